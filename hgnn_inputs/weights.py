@@ -1,0 +1,86 @@
+"""Flat weight buffers (random init) and upstream gradients.
+
+Layout of one message-passing layer (float32, matrices row-major [in, out]):
+    W1[(2H+1), H]  rows 0..H-1 act on h_i (destination), H..2H-1 on h_j (source), row 2H on d^2
+    b1[H]  W2[H,H]  b2[H]  wx[H]  W3[2H,H] (rows 0..H-1 on h_i, H..2H-1 on M_i)  b3[H]  W4[H,H]  b4[H]
+Layout of one source's decoding branch:
+    We1[H,Hh] be1[Hh] We2[Hh] be2[1]   (energy head)   Wf1[H,Hh] bf1[Hh] Wf2[Hh] bf2[1]   (force head)
+All S branches are stored back to back.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+ZMAX = 94  # embedding table has ZMAX+1 rows, indexed by atomic number
+
+LAYER_FIELDS = ("W1", "b1", "W2", "b2", "wx", "W3", "b3", "W4", "b4")
+HEAD_FIELDS = ("We1", "be1", "We2", "be2", "Wf1", "bf1", "Wf2", "bf2")
+
+
+def _layer_shapes(H):
+    return {"W1": (2 * H + 1, H), "b1": (H,), "W2": (H, H), "b2": (H,), "wx": (H,),
+            "W3": (2 * H, H), "b3": (H,), "W4": (H, H), "b4": (H,)}
+
+
+def _head_shapes(H, Hh):
+    return {"We1": (H, Hh), "be1": (Hh,), "We2": (Hh,), "be2": (1,),
+            "Wf1": (H, Hh), "bf1": (Hh,), "Wf2": (Hh,), "bf2": (1,)}
+
+
+def _slices(shapes, order):
+    out, o = {}, 0
+    for k in order:
+        n = int(np.prod(shapes[k]))
+        out[k] = (o, o + n, shapes[k])
+        o += n
+    return out, o
+
+
+def layer_field_slices(H):
+    return _slices(_layer_shapes(H), LAYER_FIELDS)[0]
+
+
+def head_field_slices(H, Hh):
+    return _slices(_head_shapes(H, Hh), HEAD_FIELDS)[0]
+
+
+def layer_weight_count(H):
+    return _slices(_layer_shapes(H), LAYER_FIELDS)[1]
+
+
+def head_weight_count(H, Hh):
+    return _slices(_head_shapes(H, Hh), HEAD_FIELDS)[1]
+
+
+def _fill(rng, shapes, order, fan_in, bias_scale):
+    parts = []
+    for k in order:
+        shp = shapes[k]
+        if k in fan_in:
+            b = 1.0 / np.sqrt(fan_in[k])
+            parts.append(rng.uniform(-b, b, size=shp).ravel())
+        else:
+            parts.append(rng.uniform(-bias_scale, bias_scale, size=shp).ravel())
+    return np.concatenate(parts).astype(np.float32)
+
+
+def init_layer_weights(rng, H, bias_scale=0.1):
+    """U(-1/sqrt(fan_in), 1/sqrt(fan_in)) matrices; small non-zero biases so a dropped bias shows."""
+    fan = {"W1": 2 * H + 1, "W2": H, "wx": H, "W3": 2 * H, "W4": H}
+    return _fill(rng, _layer_shapes(H), LAYER_FIELDS, fan, bias_scale)
+
+
+def init_head_weights(rng, H, Hh, S, bias_scale=0.1):
+    fan = {"We1": H, "We2": Hh, "Wf1": H, "Wf2": Hh}
+    return np.concatenate([_fill(rng, _head_shapes(H, Hh), HEAD_FIELDS, fan, bias_scale)
+                           for _ in range(S)])
+
+
+def init_embedding(rng, H):
+    return rng.standard_normal((ZMAX + 1, H)).astype(np.float32)
+
+
+def upstream_grads(rng, G, N):
+    """Seeded stand-in for dLoss/d(energy) [G] and dLoss/d(force) [N,3] (the loss is outside the path)."""
+    return (rng.standard_normal(G).astype(np.float32),
+            rng.standard_normal((N, 3)).astype(np.float32))

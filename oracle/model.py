@@ -1,0 +1,306 @@
+"""Message-passing layer, pooling and the two-level multi-task decoder, forward and reverse mode
+(test infrastructure; see the package docstring). All arithmetic in float64.
+
+The paper names the backbone (a stack of equivariant EGNN message-passing layers shared by all
+sources, section "Numerical Results") and the decoder (one branch per dataset, each split into an
+energy-per-atom head and an atomic-force head made of fully connected layers, section "Two-level
+hierarchical MTL architecture"), and gives no formula. The layer below is the textbook E(n)-GNN
+layer with the positions held fixed during the step:
+
+  per edge e = (i <- j):   z1 = W1^T [h_i ; h_j ; d2_e] + b1     a1 = silu(z1)
+                           z2 = W2^T a1 + b2                      m_e = silu(z2)
+                           x_e = wx . m_e
+  per atom i:              M_i  = alpha * sum_{e in row i} m_e
+                           v'_i = v_i + alpha * sum_{e in row i} x_e * rvec_e   (equivariant channel)
+                           z3 = W3^T [h_i ; M_i] + b3
+                           h'_i = h_i + W4^T silu(z3) + b4
+  pooling:                 p_g = mean_{i in g} h_i
+  branch s = source_id[g]: e_g = We2_s . silu(We1_s^T p_g + be1_s) + be2_s          (energy per atom)
+                           q_i = Wf2_s . silu(Wf1_s^T h_i + bf1_s) + bf2_s,   F_i = q_i * v_i
+
+The force head is a stack of fully connected layers on the per-atom features, as the paper says;
+multiplying its scalar output into the equivariant channel v_i is this build's reading of how an
+invariant feature vector can give a force that rotates with the structure.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+_LAYER_FIELDS = ("W1", "b1", "W2", "b2", "wx", "W3", "b3", "W4", "b4")
+_HEAD_FIELDS = ("We1", "be1", "We2", "be2", "Wf1", "bf1", "Wf2", "bf2")
+
+
+def unpack_layer(flat, H):
+    """Views into one layer's flat buffer, in the documented field order (matrices are [in, out])."""
+    shapes = {"W1": (2 * H + 1, H), "b1": (H,), "W2": (H, H), "b2": (H,), "wx": (H,),
+              "W3": (2 * H, H), "b3": (H,), "W4": (H, H), "b4": (H,)}
+    out, o = {}, 0
+    for k in _LAYER_FIELDS:
+        n = int(np.prod(shapes[k]))
+        out[k] = np.asarray(flat[o:o + n]).reshape(shapes[k])
+        o += n
+    assert o == len(flat), "layer buffer has the wrong length"
+    return out
+
+
+def unpack_heads(flat, H, Hh, S):
+    """List of S dicts, one per source branch."""
+    shapes = {"We1": (H, Hh), "be1": (Hh,), "We2": (Hh,), "be2": (1,),
+              "Wf1": (H, Hh), "bf1": (Hh,), "Wf2": (Hh,), "bf2": (1,)}
+    per = sum(int(np.prod(s)) for s in shapes.values())
+    assert len(flat) == per * S, "head buffer has the wrong length"
+    out = []
+    for s in range(S):
+        d, o = {}, s * per
+        for k in _HEAD_FIELDS:
+            n = int(np.prod(shapes[k]))
+            d[k] = np.asarray(flat[o:o + n]).reshape(shapes[k])
+            o += n
+        out.append(d)
+    return out
+
+
+def pack_fields(d, order):
+    return np.concatenate([np.asarray(d[k], dtype=np.float64).ravel() for k in order])
+
+
+def silu(t):
+    return t / (1.0 + np.exp(-t))
+
+
+def dsilu(t):
+    s = 1.0 / (1.0 + np.exp(-t))
+    return s * (1.0 + t * (1.0 - s))
+
+
+# ---------------------------------------------------------------------------------------------
+# embedding
+# ---------------------------------------------------------------------------------------------
+def embed_fwd(Z, emb):
+    return np.asarray(emb, dtype=np.float64)[np.asarray(Z)]
+
+
+def embed_bwd(Z, g_h, n_rows):
+    g = np.zeros((n_rows, g_h.shape[1]), dtype=np.float64)
+    np.add.at(g, np.asarray(Z), g_h)
+    return g
+
+
+# ---------------------------------------------------------------------------------------------
+# message-passing layer
+# ---------------------------------------------------------------------------------------------
+def mp_layer_fwd(h, v, dst, col, d2, rvec, Wflat, alpha):
+    """One layer. h [N,H], v [N,3]; dst/col [E] destination/source atom of each edge; d2 [E];
+    rvec [E,3]. Returns (h', v', cache-for-backward)."""
+    h = np.asarray(h, dtype=np.float64)
+    v = np.asarray(v, dtype=np.float64)
+    N, H = h.shape
+    W = {k: np.asarray(a, dtype=np.float64) for k, a in unpack_layer(Wflat, H).items()}
+    d2 = np.asarray(d2, dtype=np.float64)
+    rvec = np.asarray(rvec, dtype=np.float64)
+    xin = np.concatenate([h[dst], h[col], d2[:, None]], axis=1)          # [E, 2H+1]
+    z1 = xin @ W["W1"] + W["b1"]
+    a1 = silu(z1)
+    z2 = a1 @ W["W2"] + W["b2"]
+    m = silu(z2)
+    x = m @ W["wx"]                                                      # [E]
+    M = np.zeros((N, H), dtype=np.float64)
+    np.add.at(M, dst, m)
+    M *= alpha
+    dv = np.zeros((N, 3), dtype=np.float64)
+    np.add.at(dv, dst, x[:, None] * rvec)
+    v_out = v + alpha * dv
+    nin = np.concatenate([h, M], axis=1)                                 # [N, 2H]
+    z3 = nin @ W["W3"] + W["b3"]
+    u = silu(z3)
+    h_out = h + u @ W["W4"] + W["b4"]
+    cache = dict(h=h, dst=np.asarray(dst), col=np.asarray(col), d2=d2, rvec=rvec, W=W, alpha=alpha,
+                 xin=xin, z1=z1, a1=a1, z2=z2, m=m, M=M, nin=nin, z3=z3, u=u)
+    return h_out, v_out, cache
+
+
+def mp_layer_bwd(cache, g_hout, g_vout):
+    """Reverse mode of mp_layer_fwd. Returns (g_h, g_v, dict of weight gradients).
+    d2 and rvec are constants of the step: no gradient flows to positions."""
+    c = cache
+    W, alpha = c["W"], c["alpha"]
+    dst, col, rvec = c["dst"], c["col"], c["rvec"]
+    N, H = c["h"].shape
+    g_hout = np.asarray(g_hout, dtype=np.float64)
+    g_vout = np.asarray(g_vout, dtype=np.float64)
+    gW = {}
+    # h' = h + u W4 + b4
+    gW["b4"] = g_hout.sum(axis=0)
+    gW["W4"] = c["u"].T @ g_hout
+    g_u = g_hout @ W["W4"].T
+    g_z3 = g_u * dsilu(c["z3"])
+    gW["b3"] = g_z3.sum(axis=0)
+    gW["W3"] = c["nin"].T @ g_z3
+    g_nin = g_z3 @ W["W3"].T
+    g_h = g_hout + g_nin[:, :H]
+    g_M = g_nin[:, H:]
+    # v' = v + alpha sum x_e rvec_e ;  M = alpha sum m_e
+    g_v = g_vout.copy()
+    g_x = alpha * np.einsum("ec,ec->e", g_vout[dst], rvec)               # [E]
+    g_m = alpha * g_M[dst] + g_x[:, None] * W["wx"][None, :]
+    gW["wx"] = c["m"].T @ g_x
+    g_z2 = g_m * dsilu(c["z2"])
+    gW["b2"] = g_z2.sum(axis=0)
+    gW["W2"] = c["a1"].T @ g_z2
+    g_a1 = g_z2 @ W["W2"].T
+    g_z1 = g_a1 * dsilu(c["z1"])
+    gW["b1"] = g_z1.sum(axis=0)
+    gW["W1"] = c["xin"].T @ g_z1
+    g_xin = g_z1 @ W["W1"].T                                             # [E, 2H+1]
+    np.add.at(g_h, dst, g_xin[:, :H])
+    np.add.at(g_h, col, g_xin[:, H:2 * H])
+    return g_h, g_v, gW
+
+
+# ---------------------------------------------------------------------------------------------
+# pooling (atoms of a graph are contiguous)
+# ---------------------------------------------------------------------------------------------
+def pool_fwd(h, graph_off, mean=True):
+    h = np.asarray(h, dtype=np.float64)
+    G = len(graph_off) - 1
+    p = np.zeros((G, h.shape[1]), dtype=np.float64)
+    for g in range(G):
+        lo, hi = int(graph_off[g]), int(graph_off[g + 1])
+        if hi > lo:
+            p[g] = h[lo:hi].sum(axis=0) / ((hi - lo) if mean else 1.0)
+    return p
+
+
+def pool_bwd(g_p, graph_off, N, mean=True):
+    g_p = np.asarray(g_p, dtype=np.float64)
+    g_h = np.zeros((N, g_p.shape[1]), dtype=np.float64)
+    for g in range(len(graph_off) - 1):
+        lo, hi = int(graph_off[g]), int(graph_off[g + 1])
+        if hi > lo:
+            g_h[lo:hi] = g_p[g] / ((hi - lo) if mean else 1.0)
+    return g_h
+
+
+# ---------------------------------------------------------------------------------------------
+# routing + heads
+# ---------------------------------------------------------------------------------------------
+def routing_plan(source_id, graph_off, S):
+    """Stable grouping of graphs (and of their atoms) by source: the rows each branch decodes.
+
+    Returns grp_graph_ptr[S+1], graph_perm[G], grp_atom_ptr[S+1], atom_perm[N], all int32."""
+    source_id = np.asarray(source_id, dtype=np.int64)
+    graph_off = np.asarray(graph_off, dtype=np.int64)
+    if source_id.size and (source_id.min() < 0 or source_id.max() >= S):
+        raise ValueError("source id out of range")
+    graph_perm = np.argsort(source_id, kind="stable").astype(np.int32)
+    gcnt = np.bincount(source_id, minlength=S)
+    grp_graph_ptr = np.zeros(S + 1, dtype=np.int32)
+    grp_graph_ptr[1:] = np.cumsum(gcnt)
+    atom_lists = [np.arange(graph_off[g], graph_off[g + 1]) for g in graph_perm]
+    atom_perm = (np.concatenate(atom_lists) if atom_lists else np.zeros(0)).astype(np.int32)
+    acnt = np.zeros(S, dtype=np.int64)
+    np.add.at(acnt, source_id, graph_off[1:] - graph_off[:-1])
+    grp_atom_ptr = np.zeros(S + 1, dtype=np.int32)
+    grp_atom_ptr[1:] = np.cumsum(acnt)
+    return grp_graph_ptr, graph_perm, grp_atom_ptr, atom_perm
+
+
+def heads_fwd(p, h, v, graph_off, source_id, Whead_flat, Hh, S):
+    """Every graph is decoded by the branch of its own source and by no other."""
+    p = np.asarray(p, dtype=np.float64)
+    h = np.asarray(h, dtype=np.float64)
+    v = np.asarray(v, dtype=np.float64)
+    G, H = p.shape
+    N = h.shape[0]
+    heads = [{k: np.asarray(a, dtype=np.float64) for k, a in d.items()}
+             for d in unpack_heads(Whead_flat, H, Hh, S)]
+    energy = np.zeros(G, dtype=np.float64)
+    q = np.zeros(N, dtype=np.float64)
+    ze = np.zeros((G, Hh), dtype=np.float64)
+    zf = np.zeros((N, Hh), dtype=np.float64)
+    for g in range(G):
+        w = heads[int(source_id[g])]
+        lo, hi = int(graph_off[g]), int(graph_off[g + 1])
+        ze[g] = p[g] @ w["We1"] + w["be1"]
+        energy[g] = silu(ze[g]) @ w["We2"] + w["be2"][0]
+        zf[lo:hi] = h[lo:hi] @ w["Wf1"] + w["bf1"]
+        q[lo:hi] = silu(zf[lo:hi]) @ w["Wf2"] + w["bf2"][0]
+    force = q[:, None] * v
+    cache = dict(p=p, h=h, v=v, graph_off=np.asarray(graph_off), source_id=np.asarray(source_id),
+                 heads=heads, ze=ze, zf=zf, q=q, Hh=Hh, S=S)
+    return energy, force, cache
+
+
+def heads_bwd(cache, g_energy, g_force):
+    """Returns (g_p [G,H], g_h [N,H], g_v [N,3], list of S dicts of head-weight gradients)."""
+    c = cache
+    p, h, v = c["p"], c["h"], c["v"]
+    G, H = p.shape
+    N = h.shape[0]
+    g_energy = np.asarray(g_energy, dtype=np.float64)
+    g_force = np.asarray(g_force, dtype=np.float64)
+    gheads = [{k: np.zeros_like(a) for k, a in w.items()} for w in c["heads"]]
+    g_p = np.zeros_like(p)
+    g_h = np.zeros_like(h)
+    g_q = np.einsum("nc,nc->n", g_force, v)
+    g_v = c["q"][:, None] * g_force
+    for g in range(G):
+        s = int(c["source_id"][g])
+        w, gw = c["heads"][s], gheads[s]
+        lo, hi = int(c["graph_off"][g]), int(c["graph_off"][g + 1])
+        # energy head
+        ae = silu(c["ze"][g])
+        gw["be2"][0] += g_energy[g]
+        gw["We2"] += g_energy[g] * ae
+        g_ze = g_energy[g] * w["We2"] * dsilu(c["ze"][g])
+        gw["be1"] += g_ze
+        gw["We1"] += np.outer(p[g], g_ze)
+        g_p[g] = w["We1"] @ g_ze
+        # force head
+        af = silu(c["zf"][lo:hi])
+        gq = g_q[lo:hi]
+        gw["bf2"][0] += gq.sum()
+        gw["Wf2"] += af.T @ gq
+        g_zf = gq[:, None] * w["Wf2"][None, :] * dsilu(c["zf"][lo:hi])
+        gw["bf1"] += g_zf.sum(axis=0)
+        gw["Wf1"] += h[lo:hi].T @ g_zf
+        g_h[lo:hi] = g_zf @ w["Wf1"].T
+    return g_p, g_h, g_v, gheads
+
+
+# ---------------------------------------------------------------------------------------------
+# whole step
+# ---------------------------------------------------------------------------------------------
+def step_fwd_bwd(Z, graph_off, source_id, graph, emb, layer_weights, head_weights, Hh, S, alpha,
+                 g_energy=None, g_force=None, keep_layers=False):
+    """Embedding -> L layers -> mean pool -> heads, then (if upstream gradients are given) the
+    whole reverse pass. `graph` is the dict returned by oracle.radius_graph."""
+    H = emb.shape[1]
+    N = len(Z)
+    dst, col, d2, rvec = graph["dst"], graph["col"], graph["d2"], graph["rvec"]
+    h = embed_fwd(Z, emb)
+    v = np.zeros((N, 3), dtype=np.float64)
+    caches, hs = [], [h]
+    for Wl in layer_weights:
+        h, v, c = mp_layer_fwd(h, v, dst, col, d2, rvec, Wl, alpha)
+        caches.append(c)
+        if keep_layers:
+            hs.append(h)
+    p = pool_fwd(h, graph_off)
+    energy, force, hc = heads_fwd(p, h, v, graph_off, source_id, head_weights, Hh, S)
+    out = dict(h=h, v=v, p=p, energy=energy, force=force, hs=hs)
+    if g_energy is None:
+        return out
+    g_p, g_h, g_v, gheads = heads_bwd(hc, g_energy, g_force)
+    g_h = g_h + pool_bwd(g_p, graph_off, N)
+    g_layers = []
+    for c in reversed(caches):
+        g_h, g_v, gW = mp_layer_bwd(c, g_h, g_v)
+        g_layers.append(pack_fields(gW, _LAYER_FIELDS))
+    g_layers.reverse()
+    out.update(
+        g_emb=embed_bwd(Z, g_h, emb.shape[0]), g_layers=g_layers,
+        g_heads=np.concatenate([pack_fields(d, _HEAD_FIELDS) for d in gheads]),
+        g_h0=g_h, g_v0=g_v,
+    )
+    return out

@@ -1,0 +1,500 @@
+"""Pins of the oracle's layer / pooling / decoder arithmetic against things other than itself."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from hgnn_inputs import (concat_graphs, head_field_slices, head_weight_count, init_embedding,
+                         init_head_weights, init_layer_weights, layer_field_slices,
+                         layer_weight_count, small_mixed_batch, upstream_grads)
+from hgnn_inputs.structures import Batch
+
+
+def make_problem(seed=0, H=8, Hh=6, L=2, S=3, rc=4.0, batch=None):
+    b = batch if batch is not None else small_mixed_batch(seed, S=S)
+    rng = np.random.default_rng(seed + 1000)
+    g = oracle.radius_graph(b.pos, b.graph_off, b.cell, b.pbc, rc)
+    emb = init_embedding(rng, H).astype(np.float64)
+    Ws = [init_layer_weights(rng, H).astype(np.float64) for _ in range(L)]
+    Wh = init_head_weights(rng, H, Hh, S).astype(np.float64)
+    gE, gF = upstream_grads(rng, b.G, b.N)
+    alpha = 1.0 / max(1.0, g["E"] / b.N)
+    return dict(b=b, g=g, emb=emb, Ws=Ws, Wh=Wh, gE=gE.astype(np.float64), gF=gF.astype(np.float64),
+                alpha=alpha, H=H, Hh=Hh, L=L, S=S, rc=rc)
+
+
+def run(P, grads=True, **kw):
+    b = kw.get("b", P["b"])
+    return oracle.step_fwd_bwd(b.Z, b.graph_off, b.source_id, kw.get("g", P["g"]), kw.get("emb", P["emb"]),
+                               kw.get("Ws", P["Ws"]), kw.get("Wh", P["Wh"]), P["Hh"], P["S"], P["alpha"],
+                               P["gE"] if grads else None, P["gF"] if grads else None)
+
+
+def no_borderline(g, rc, tol=1e-3):
+    return np.all(np.abs(np.sqrt(g["d2"].astype(np.float64)) - rc) > tol)
+
+
+# ---------------------------------------------------------------------------------------------
+# forward: brute force with scalar Python loops on a tiny input
+# ---------------------------------------------------------------------------------------------
+def _silu(t):
+    return t / (1.0 + math.exp(-t))
+
+
+def scalar_forward(P):
+    """Edge-by-edge, feature-by-feature evaluation reading the flat buffers by explicit index."""
+    b, g, H, Hh, S = P["b"], P["g"], P["H"], P["Hh"], P["S"]
+    N = b.N
+    h = [[float(P["emb"][b.Z[i], k]) for k in range(H)] for i in range(N)]
+    v = [[0.0] * 3 for _ in range(N)]
+    for Wl in P["Ws"]:
+        sl = layer_field_slices(H)
+        o = {k: sl[k][0] for k in sl}
+        M = [[0.0] * H for _ in range(N)]
+        dv = [[0.0] * 3 for _ in range(N)]
+        for e in range(g["E"]):
+            i, j = int(g["dst"][e]), int(g["col"][e])
+            d2 = float(g["d2"][e])
+            a1 = []
+            for n in range(H):
+                t = float(Wl[o["b1"] + n])
+                for k in range(H):
+                    t += h[i][k] * Wl[o["W1"] + k * H + n]
+                    t += h[j][k] * Wl[o["W1"] + (H + k) * H + n]
+                t += d2 * Wl[o["W1"] + 2 * H * H + n]
+                a1.append(_silu(t))
+            x = 0.0
+            for n in range(H):
+                t = float(Wl[o["b2"] + n])
+                for k in range(H):
+                    t += a1[k] * Wl[o["W2"] + k * H + n]
+                m = _silu(t)
+                M[i][n] += m
+                x += Wl[o["wx"] + n] * m
+            for c in range(3):
+                dv[i][c] += x * float(g["rvec"][e, c])
+        hn = []
+        for i in range(N):
+            u = []
+            for n in range(H):
+                t = float(Wl[o["b3"] + n])
+                for k in range(H):
+                    t += h[i][k] * Wl[o["W3"] + k * H + n]
+                    t += P["alpha"] * M[i][k] * Wl[o["W3"] + (H + k) * H + n]
+                u.append(_silu(t))
+            row = []
+            for n in range(H):
+                t = h[i][n] + float(Wl[o["b4"] + n])
+                for k in range(H):
+                    t += u[k] * Wl[o["W4"] + k * H + n]
+                row.append(t)
+            hn.append(row)
+            for c in range(3):
+                v[i][c] += P["alpha"] * dv[i][c]
+        h = hn
+    per = head_weight_count(H, Hh)
+    hs = head_field_slices(H, Hh)
+    energy, force = [], [[0.0] * 3 for _ in range(N)]
+    for gi in range(b.G):
+        base = int(b.source_id[gi]) * per
+        lo, hi = int(b.graph_off[gi]), int(b.graph_off[gi + 1])
+        p = [sum(h[i][k] for i in range(lo, hi)) / (hi - lo) for k in range(H)]
+        e = float(P["Wh"][base + hs["be2"][0]])
+        for n in range(Hh):
+            t = float(P["Wh"][base + hs["be1"][0] + n])
+            for k in range(H):
+                t += p[k] * P["Wh"][base + hs["We1"][0] + k * Hh + n]
+            e += _silu(t) * P["Wh"][base + hs["We2"][0] + n]
+        energy.append(e)
+        for i in range(lo, hi):
+            q = float(P["Wh"][base + hs["bf2"][0]])
+            for n in range(Hh):
+                t = float(P["Wh"][base + hs["bf1"][0] + n])
+                for k in range(H):
+                    t += h[i][k] * P["Wh"][base + hs["Wf1"][0] + k * Hh + n]
+                q += _silu(t) * P["Wh"][base + hs["Wf2"][0] + n]
+            for c in range(3):
+                force[i][c] = q * v[i][c]
+    return np.array(h), np.array(v), np.array(energy), np.array(force)
+
+
+def test_forward_equals_scalar_brute_force():
+    P = make_problem(seed=3, H=4, Hh=3, L=2, S=2, rc=3.2,
+                     batch=small_mixed_batch(3, n_mol=2, n_cry=1, S=2, mol_atoms=(3, 6), cry_atoms=(2, 4)))
+    assert 20 < P["g"]["E"] < 2000
+    out = run(P, grads=False)
+    h, v, e, f = scalar_forward(P)
+    assert np.allclose(out["h"], h, rtol=1e-12, atol=1e-12)
+    assert np.allclose(out["v"], v, rtol=1e-12, atol=1e-12)
+    assert np.allclose(out["energy"], e, rtol=1e-12, atol=1e-12)
+    assert np.allclose(out["force"], f, rtol=1e-12, atol=1e-12)
+    assert np.abs(f).max() > 1e-4
+
+
+# ---------------------------------------------------------------------------------------------
+# aggregation = dense adjacency product; adjoint identity
+# ---------------------------------------------------------------------------------------------
+def test_aggregation_equals_dense_adjacency_product():
+    P = make_problem(seed=4)
+    b, g = P["b"], P["g"]
+    h0 = oracle.embed_fwd(b.Z, P["emb"])
+    _, v1, c = oracle.mp_layer_fwd(h0, np.zeros((b.N, 3)), g["dst"], g["col"], g["d2"], g["rvec"],
+                                   P["Ws"][0], P["alpha"])
+    A = np.zeros((b.N, g["E"]))
+    for e in range(g["E"]):
+        A[g["dst"][e], e] = 1.0
+    assert np.allclose(c["M"], P["alpha"] * (A @ c["m"]), rtol=1e-13, atol=1e-13)
+    x = c["m"] @ oracle.unpack_layer(P["Ws"][0], P["H"])["wx"]
+    assert np.allclose(v1, P["alpha"] * (A @ (x[:, None] * g["rvec"])), rtol=1e-13, atol=1e-13)
+    # adjoint identity <scatter(m), y> = <m, gather(y)>
+    y = np.random.default_rng(0).standard_normal((b.N, P["H"]))
+    assert np.isclose(np.sum((A @ c["m"]) * y), np.sum(c["m"] * y[g["dst"]]))
+
+
+# ---------------------------------------------------------------------------------------------
+# symmetries
+# ---------------------------------------------------------------------------------------------
+def random_rotation(rng):
+    q, r = np.linalg.qr(rng.standard_normal((3, 3)))
+    q = q * np.sign(np.diag(r))
+    if np.linalg.det(q) < 0:
+        q[:, 0] = -q[:, 0]
+    return q
+
+
+def transformed(P, pos=None, cell=None, perm=None, gperm=None):
+    b = P["b"]
+    nb = Batch(pos=(b.pos if pos is None else pos).astype(np.float32), Z=b.Z.copy(),
+               graph_off=b.graph_off.copy(), cell=(b.cell if cell is None else cell).astype(np.float32),
+               pbc=b.pbc.copy(), source_id=b.source_id.copy())
+    if perm is not None:
+        nb.pos, nb.Z = nb.pos[perm], nb.Z[perm]
+    if gperm is not None:
+        graphs = []
+        for g in gperm:
+            lo, hi = b.graph_off[g], b.graph_off[g + 1]
+            graphs.append((nb.pos[lo:hi], nb.Z[lo:hi], nb.cell[g] if b.pbc[g] else None))
+        nb = concat_graphs(graphs, b.source_id[gperm])
+    g = oracle.radius_graph(nb.pos, nb.graph_off, nb.cell, nb.pbc, P["rc"], extra_images=1)
+    return nb, g
+
+
+def test_rotation_translation_invariance_and_force_equivariance():
+    P = make_problem(seed=6, rc=3.6)
+    assert no_borderline(P["g"], P["rc"])
+    out = run(P, grads=False)
+    rng = np.random.default_rng(9)
+    R = random_rotation(rng)
+    t = np.array([0.7, -0.3, 1.1])
+    b = P["b"]
+    pos2 = b.pos.astype(np.float64) @ R.T + t
+    cell2 = b.cell.astype(np.float64) @ R.T
+    nb, g2 = transformed(P, pos=pos2, cell=cell2)
+    assert g2["E"] == P["g"]["E"] and np.array_equal(g2["col"], P["g"]["col"])
+    out2 = run(P, grads=False, b=nb, g=g2)
+    assert np.allclose(out2["energy"], out["energy"], rtol=1e-5, atol=1e-6)
+    assert np.allclose(out2["h"], out["h"], rtol=1e-5, atol=1e-6)
+    assert np.allclose(out2["force"], out["force"] @ R.T, rtol=1e-4, atol=1e-6)
+    assert np.abs(out["force"]).max() > 1e-3
+    # a rotated force differs from the unrotated one: the check above is not vacuous
+    assert not np.allclose(out2["force"], out["force"], rtol=1e-2, atol=1e-4)
+
+
+def test_permutation_equivariance():
+    P = make_problem(seed=8)
+    out = run(P, grads=False)
+    b = P["b"]
+    rng = np.random.default_rng(1)
+    perm = np.arange(b.N)
+    for g in range(b.G):
+        lo, hi = b.graph_off[g], b.graph_off[g + 1]
+        perm[lo:hi] = lo + rng.permutation(hi - lo)
+    nb, g2 = transformed(P, perm=perm)
+    out2 = run(P, grads=False, b=nb, g=g2)
+    assert np.allclose(out2["energy"], out["energy"], rtol=1e-12)
+    assert np.allclose(out2["force"], out["force"][perm], rtol=1e-10, atol=1e-12)
+    # graph order
+    gperm = rng.permutation(b.G)
+    nb, g3 = transformed(P, gperm=gperm)
+    out3 = run(P, grads=False, b=nb, g=g3)
+    assert np.allclose(out3["energy"], out["energy"][gperm], rtol=1e-12)
+
+
+def test_supercell_gives_same_energy_per_atom_and_duplicated_forces():
+    rng = np.random.default_rng(2)
+    from hgnn_inputs.structures import make_crystal
+    pos, z, cell = make_crystal(rng, 5, 3.0, 5.0, 0.9, 1, 30, max_density=0.2)
+    b1 = concat_graphs([(pos, z, cell)])
+    pos2 = np.concatenate([pos, pos + cell[0]], axis=0)
+    cell2 = cell.copy()
+    cell2[0] *= 2
+    b2 = concat_graphs([(pos2, np.concatenate([z, z]), cell2)])
+    rc = 4.5
+    P1 = make_problem(seed=1, S=1, rc=rc, batch=b1)
+    g2 = oracle.radius_graph(b2.pos, b2.graph_off, b2.cell, b2.pbc, rc)
+    assert no_borderline(P1["g"], rc, 1e-4)
+    assert g2["E"] == 2 * P1["g"]["E"]
+    assert np.array_equal(np.diff(g2["row_ptr"]), np.tile(np.diff(P1["g"]["row_ptr"]), 2))
+    o1 = run(P1, grads=False)
+    o2 = run(P1, grads=False, b=b2, g=g2)
+    assert np.allclose(o2["energy"], o1["energy"], rtol=1e-6)
+    assert np.allclose(o2["force"], np.tile(o1["force"], (2, 1)), rtol=1e-4, atol=1e-6)
+    assert any(i == j for i, j in zip(P1["g"]["dst"], P1["g"]["col"]))   # self images were needed
+
+
+# ---------------------------------------------------------------------------------------------
+# layout conventions of W1 / W3 (which rows act on what)
+# ---------------------------------------------------------------------------------------------
+def test_weight_row_blocks_act_on_the_documented_inputs():
+    P = make_problem(seed=10, L=1)
+    b, g, H = P["b"], P["g"], P["H"]
+    sl = layer_field_slices(H)
+    rng = np.random.default_rng(0)
+    h0 = rng.standard_normal((b.N, H))
+    v0 = np.zeros((b.N, 3))
+
+    def msgs(W, h):
+        return oracle.mp_layer_fwd(h, v0, g["dst"], g["col"], g["d2"], g["rvec"], W, 1.0)[2]["m"]
+
+    W = P["Ws"][0].copy()
+    o = sl["W1"][0]
+    # zero the block acting on the source: messages must not change when only source features change
+    Wa = W.copy()
+    Wa[o + H * H:o + 2 * H * H] = 0.0
+    e = int(np.argmax(g["dst"] != g["col"]))
+    h1 = h0.copy()
+    h1[g["col"][e]] += 1.0
+    rows_of_src = g["dst"] == g["col"][e]
+    m0, m1 = msgs(Wa, h0), msgs(Wa, h1)
+    assert np.allclose(m0[~rows_of_src], m1[~rows_of_src])
+    assert not np.allclose(m0[rows_of_src], m1[rows_of_src])
+    # zero the d2 row: messages independent of distances
+    Wb = W.copy()
+    Wb[o + 2 * H * H:o + 2 * H * H + H] = 0.0
+    c0 = oracle.mp_layer_fwd(h0, v0, g["dst"], g["col"], g["d2"], g["rvec"], Wb, 1.0)[2]["m"]
+    c1 = oracle.mp_layer_fwd(h0, v0, g["dst"], g["col"], g["d2"] * 2, g["rvec"], Wb, 1.0)[2]["m"]
+    assert np.allclose(c0, c1)
+    assert not np.allclose(msgs(W, h0), oracle.mp_layer_fwd(h0, v0, g["dst"], g["col"], g["d2"] * 2,
+                                                            g["rvec"], W, 1.0)[2]["m"])
+    # W2 = 0 and b2 = 0: no message, the layer reduces to the node MLP on [h ; 0], v unchanged
+    Wc = W.copy()
+    Wc[sl["W2"][0]:sl["W2"][1]] = 0.0
+    Wc[sl["b2"][0]:sl["b2"][1]] = 0.0
+    hout, vout, _ = oracle.mp_layer_fwd(h0, v0 + 1.0, g["dst"], g["col"], g["d2"], g["rvec"], Wc, 1.0)
+    U = oracle.unpack_layer(Wc, H)
+    z3 = h0 @ U["W3"][:H] + U["b3"]
+    want = h0 + (z3 / (1 + np.exp(-z3))) @ U["W4"] + U["b4"]
+    assert np.allclose(hout, want) and np.allclose(vout, v0 + 1.0)
+
+
+# ---------------------------------------------------------------------------------------------
+# decoder routing
+# ---------------------------------------------------------------------------------------------
+def test_equal_heads_equal_single_head_and_heads_are_independent():
+    P = make_problem(seed=12, S=3)
+    H, Hh = P["H"], P["Hh"]
+    per = head_weight_count(H, Hh)
+    one = P["Wh"][:per]
+    Wsame = np.tile(one, 3)
+    out3 = run(P, grads=False, Wh=Wsame)
+    b = P["b"]
+    P1 = dict(P, S=1)
+    b1 = Batch(b.pos, b.Z, b.graph_off, b.cell, b.pbc, np.zeros_like(b.source_id))
+    out1 = run(P1, grads=False, b=b1, Wh=one)
+    assert np.allclose(out3["energy"], out1["energy"]) and np.allclose(out3["force"], out1["force"])
+    # changing head t changes no output of graphs of another source
+    t = int(b.source_id[0])
+    W2 = P["Wh"].copy()
+    W2[t * per:(t + 1) * per] += 0.3
+    o0, o2 = run(P, grads=False), run(P, grads=False, Wh=W2)
+    other = b.source_id != t
+    assert other.any() and (~other).any()
+    assert np.array_equal(o0["energy"][other], o2["energy"][other])
+    assert not np.allclose(o0["energy"][~other], o2["energy"][~other])
+    gid = np.searchsorted(b.graph_off, np.arange(b.N), side="right") - 1
+    assert np.array_equal(o0["force"][other[gid]], o2["force"][other[gid]])
+
+
+def test_routing_plan_by_python_loops():
+    rng = np.random.default_rng(4)
+    S, G = 4, 13
+    src = rng.integers(0, S, size=G)
+    sizes = rng.integers(1, 6, size=G)
+    off = np.concatenate([[0], np.cumsum(sizes)])
+    ggp, gperm, gap, aperm = oracle.routing_plan(src, off, S)
+    want_g, want_a, gp, ap = [], [], [0], [0]
+    for s in range(S):
+        for g in range(G):
+            if src[g] == s:
+                want_g.append(g)
+                want_a.extend(range(off[g], off[g + 1]))
+        gp.append(len(want_g))
+        ap.append(len(want_a))
+    assert gperm.tolist() == want_g and aperm.tolist() == want_a
+    assert ggp.tolist() == gp and gap.tolist() == ap
+    with pytest.raises(ValueError):
+        oracle.routing_plan(np.array([0, S]), np.array([0, 1, 2]), S)
+
+
+def test_absent_source_has_exactly_zero_gradient():
+    P = make_problem(seed=14, S=4)
+    b = P["b"]
+    src = b.source_id.copy()
+    src[src == 2] = 1
+    b2 = Batch(b.pos, b.Z, b.graph_off, b.cell, b.pbc, src)
+    out = run(P, b=b2)
+    per = head_weight_count(P["H"], P["Hh"])
+    assert np.all(out["g_heads"][2 * per:3 * per] == 0.0)
+    assert np.any(out["g_heads"][1 * per:2 * per] != 0.0)
+
+
+# ---------------------------------------------------------------------------------------------
+# backward: finite differences, autograd, linearity
+# ---------------------------------------------------------------------------------------------
+def loss_of(P, emb, Ws, Wh):
+    o = run(P, grads=False, emb=emb, Ws=Ws, Wh=Wh)
+    return float(np.sum(P["gE"] * o["energy"]) + np.sum(P["gF"] * o["force"]))
+
+
+def test_backward_by_central_finite_differences_all_parameters():
+    P = make_problem(seed=16, H=6, Hh=5, L=2, S=3)
+    out = run(P)
+    rng = np.random.default_rng(0)
+    eps = 1e-6
+    # one random direction over everything
+    for trial in range(2):
+        d_emb = rng.standard_normal(P["emb"].shape)
+        d_Ws = [rng.standard_normal(w.shape) for w in P["Ws"]]
+        d_Wh = rng.standard_normal(P["Wh"].shape)
+        ana = (np.sum(out["g_emb"] * d_emb) + sum(np.sum(g * d) for g, d in zip(out["g_layers"], d_Ws))
+               + np.sum(out["g_heads"] * d_Wh))
+        lp = loss_of(P, P["emb"] + eps * d_emb, [w + eps * d for w, d in zip(P["Ws"], d_Ws)], P["Wh"] + eps * d_Wh)
+        lm = loss_of(P, P["emb"] - eps * d_emb, [w - eps * d for w, d in zip(P["Ws"], d_Ws)], P["Wh"] - eps * d_Wh)
+        num = (lp - lm) / (2 * eps)
+        assert abs(num - ana) <= 1e-6 * max(1.0, abs(ana)), (num, ana)
+
+
+def test_backward_by_finite_differences_field_by_field():
+    """A direction confined to one field at a time: a wrong small field (a bias, wx) cannot hide."""
+    P = make_problem(seed=17, H=5, Hh=4, L=2, S=2)
+    out = run(P)
+    rng = np.random.default_rng(1)
+    eps = 1e-6
+    H, Hh = P["H"], P["Hh"]
+    for l in range(P["L"]):
+        for name, (lo, hi, _) in layer_field_slices(H).items():
+            d = np.zeros_like(P["Ws"][l])
+            d[lo:hi] = rng.standard_normal(hi - lo)
+            Wp = [w.copy() for w in P["Ws"]]
+            Wm = [w.copy() for w in P["Ws"]]
+            Wp[l] += eps * d
+            Wm[l] -= eps * d
+            num = (loss_of(P, P["emb"], Wp, P["Wh"]) - loss_of(P, P["emb"], Wm, P["Wh"])) / (2 * eps)
+            ana = np.sum(out["g_layers"][l] * d)
+            assert abs(num - ana) <= 2e-6 * max(1e-2, abs(ana)), (l, name, num, ana)
+    per = head_weight_count(H, Hh)
+    for s in range(P["S"]):
+        for name, (lo, hi, _) in head_field_slices(H, Hh).items():
+            d = np.zeros_like(P["Wh"])
+            d[s * per + lo:s * per + hi] = rng.standard_normal(hi - lo)
+            num = (loss_of(P, P["emb"], P["Ws"], P["Wh"] + eps * d)
+                   - loss_of(P, P["emb"], P["Ws"], P["Wh"] - eps * d)) / (2 * eps)
+            ana = np.sum(out["g_heads"] * d)
+            assert abs(num - ana) <= 2e-6 * max(1e-2, abs(ana)), (s, name, num, ana)
+
+
+def torch_loss(P, emb, Ws, Wh):
+    """The forward written with torch ops; autograd then derives a backward that owes nothing to
+    the oracle's hand-written reverse pass."""
+    b, g, H, Hh, S = P["b"], P["g"], P["H"], P["Hh"], P["S"]
+    dst = torch.as_tensor(g["dst"], dtype=torch.long)
+    col = torch.as_tensor(g["col"], dtype=torch.long)
+    d2 = torch.as_tensor(g["d2"], dtype=torch.float64)
+    rvec = torch.as_tensor(g["rvec"], dtype=torch.float64)
+    h = emb[torch.as_tensor(b.Z, dtype=torch.long)]
+    v = torch.zeros(b.N, 3, dtype=torch.float64)
+    silu = torch.nn.functional.silu
+    for W in Ws:
+        f = {k: W[lo:hi].reshape(shp) for k, (lo, hi, shp) in layer_field_slices(H).items()}
+        m = silu(silu(torch.cat([h[dst], h[col], d2[:, None]], 1) @ f["W1"] + f["b1"]) @ f["W2"] + f["b2"])
+        M = torch.zeros(b.N, H, dtype=torch.float64).index_add(0, dst, m) * P["alpha"]
+        v = v + P["alpha"] * torch.zeros(b.N, 3, dtype=torch.float64).index_add(0, dst, (m @ f["wx"])[:, None] * rvec)
+        h = h + silu(torch.cat([h, M], 1) @ f["W3"] + f["b3"]) @ f["W4"] + f["b4"]
+    per = head_weight_count(H, Hh)
+    loss = torch.zeros((), dtype=torch.float64)
+    gE = torch.as_tensor(P["gE"])
+    gF = torch.as_tensor(P["gF"])
+    for gi in range(b.G):
+        s = int(b.source_id[gi])
+        f = {k: Wh[s * per + lo:s * per + hi].reshape(shp) for k, (lo, hi, shp) in head_field_slices(H, Hh).items()}
+        lo, hi = int(b.graph_off[gi]), int(b.graph_off[gi + 1])
+        e = silu(h[lo:hi].mean(0) @ f["We1"] + f["be1"]) @ f["We2"] + f["be2"][0]
+        q = silu(h[lo:hi] @ f["Wf1"] + f["bf1"]) @ f["Wf2"] + f["bf2"][0]
+        loss = loss + gE[gi] * e + torch.sum(gF[lo:hi] * (q[:, None] * v[lo:hi]))
+    return loss
+
+
+def test_backward_equals_torch_autograd():
+    P = make_problem(seed=18, H=8, Hh=6, L=3, S=3)
+    out = run(P)
+    emb = torch.tensor(P["emb"], requires_grad=True)
+    Ws = [torch.tensor(w, requires_grad=True) for w in P["Ws"]]
+    Wh = torch.tensor(P["Wh"], requires_grad=True)
+    loss = torch_loss(P, emb, Ws, Wh)
+    loss.backward()
+    o = run(P, grads=False)
+    assert np.isclose(loss.item(), np.sum(P["gE"] * o["energy"]) + np.sum(P["gF"] * o["force"]), rtol=1e-12)
+
+    def close(a, b):
+        return np.max(np.abs(a - b)) <= 1e-10 * max(1.0, np.max(np.abs(b)))
+
+    assert close(out["g_emb"], emb.grad.numpy())
+    for l in range(P["L"]):
+        assert close(out["g_layers"][l], Ws[l].grad.numpy()), l
+    assert close(out["g_heads"], Wh.grad.numpy())
+
+
+def test_gradient_of_a_batch_is_the_sum_over_its_halves():
+    """What data-parallel averaging of the shared-layer gradients relies on."""
+    P = make_problem(seed=20, S=2)
+    b = P["b"]
+    full = run(P)
+    k = b.G // 2
+    parts = []
+    for lo_g, hi_g in ((0, k), (k, b.G)):
+        graphs = [(b.pos[b.graph_off[g]:b.graph_off[g + 1]], b.Z[b.graph_off[g]:b.graph_off[g + 1]],
+                   b.cell[g] if b.pbc[g] else None) for g in range(lo_g, hi_g)]
+        nb = concat_graphs(graphs, b.source_id[lo_g:hi_g])
+        a0, a1 = b.graph_off[lo_g], b.graph_off[hi_g]
+        Ph = dict(P, b=nb, g=oracle.radius_graph(nb.pos, nb.graph_off, nb.cell, nb.pbc, P["rc"]),
+                  gE=P["gE"][lo_g:hi_g], gF=P["gF"][a0:a1])
+        parts.append(run(Ph))
+    for l in range(P["L"]):
+        assert np.allclose(full["g_layers"][l], parts[0]["g_layers"][l] + parts[1]["g_layers"][l], rtol=1e-10, atol=1e-12)
+    assert np.allclose(full["g_heads"], parts[0]["g_heads"] + parts[1]["g_heads"], rtol=1e-10, atol=1e-12)
+    assert np.allclose(full["g_emb"], parts[0]["g_emb"] + parts[1]["g_emb"], rtol=1e-10, atol=1e-12)
+
+
+def test_parameter_count_with_all_heads_resident():
+    """Memory with every branch on one device: P_s + N_h * P_h (paper, section 'Multi-task parallelism')."""
+    H, Hh, L, S = 16, 12, 3, 5
+    Ps = L * layer_weight_count(H)
+    Ph = head_weight_count(H, Hh)
+    assert layer_weight_count(H) == 6 * H * H + 6 * H
+    assert Ph == 2 * (H * Hh + 2 * Hh + 1)
+    rng = np.random.default_rng(0)
+    total = sum(init_layer_weights(rng, H).size for _ in range(L)) + init_head_weights(rng, H, Hh, S).size
+    assert total == Ps + S * Ph
+
+
+def test_isolated_atom_keeps_v_and_gets_zero_aggregate():
+    pos = np.array([[0, 0, 0], [1.0, 0, 0], [30.0, 0, 0]], dtype=np.float32)
+    b = concat_graphs([(pos, np.array([1, 6, 8], np.int32))])
+    P = make_problem(seed=2, S=1, rc=3.0, batch=b, L=1)
+    assert P["g"]["E"] == 2 and np.diff(P["g"]["row_ptr"]).tolist() == [1, 1, 0]
+    h0 = oracle.embed_fwd(b.Z, P["emb"])
+    _, v, c = oracle.mp_layer_fwd(h0, np.ones((3, 3)), P["g"]["dst"], P["g"]["col"], P["g"]["d2"],
+                                  P["g"]["rvec"], P["Ws"][0], 1.0)
+    assert np.all(c["M"][2] == 0.0) and np.all(v[2] == 1.0) and np.any(c["M"][0] != 0.0)
