@@ -1,0 +1,194 @@
+/*
+ * libhgnn -- one GPU's share of a HydraGNN multi-task pre-training step on MI355X (gfx950).
+ *
+ * The step (paper: shared message-passing stack, then one decoding branch per dataset, each branch
+ * split into an energy-per-atom head and an atomic-force head; sections "Two-level hierarchical MTL
+ * architecture" and "Multi-task parallelism"; EGNN backbone named in section "Numerical Results"):
+ *
+ *   radius graph -> embedding -> L x message-passing layer -> mean pool -> per-source heads
+ *   and the reverse pass of all of it.
+ *
+ * Conventions
+ *  - Plain C ABI. Every function returns an hgnn_status (0 = ok, negative = error) and never throws.
+ *    hgnn_last_error_string() gives the text of the calling thread's last error.
+ *  - Unless a name ends in _host, every pointer is a DEVICE pointer to a contiguous row-major array,
+ *    aligned to 16 bytes. The caller owns every buffer (inputs, outputs, saved activations and
+ *    workspaces); the library allocates no device memory and keeps no pointer after a call returns.
+ *  - `stream` is a hipStream_t passed as void*. Calls only enqueue work on it, except where a
+ *    function is documented to synchronise.
+ *  - Index type is int32. N atoms, G graphs, E directed edges, H hidden width, S sources.
+ *    Edge e = (i <- j, s): i = dst[e] is the destination atom, j = col[e] the source atom, s the
+ *    integer lattice shift applied to j.
+ *  - H must be 64, 128 or 256 (tile granularity of the matrix-core kernels). Head width Hh == H.
+ *  - dtype selects the GEMM operand type: HGNN_F32 (fp32 matrix cores) or HGNN_BF16 (operands rounded
+ *    to bf16 on load, fp32 accumulation). Activations, aggregation, biases and SiLU stay fp32.
+ *  - Gradient outputs are overwritten, not accumulated, unless said otherwise.
+ *  - Results are deterministic: no floating-point atomics anywhere, all reductions in a fixed order.
+ */
+#ifndef HGNN_H
+#define HGNN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  HGNN_OK = 0,
+  HGNN_ERR_NULLPTR = -1,
+  HGNN_ERR_BAD_SHAPE = -2,
+  HGNN_ERR_BAD_OFFSETS = -3,
+  HGNN_ERR_BAD_CELL = -4,
+  HGNN_ERR_BAD_SOURCE_ID = -5,
+  HGNN_ERR_WORKSPACE_TOO_SMALL = -6,
+  HGNN_ERR_OVERFLOW = -7,
+  HGNN_ERR_HIP = -8,
+  HGNN_ERR_UNIMPLEMENTED = -9
+} hgnn_status;
+
+enum { HGNN_F32 = 0, HGNN_BF16 = 1 };
+enum { HGNN_POOL_SUM = 0, HGNN_POOL_MEAN = 1 };
+enum { HGNN_ZMAX = 94 }; /* embedding table has HGNN_ZMAX+1 rows */
+
+const char* hgnn_last_error_string(void);
+int32_t hgnn_version(void);
+
+/* ---------------------------------------------------------------------------------------------
+ * Radius graph (the "radius graphs of atomistic structures" the shared message-passing stack runs
+ * on; the paper gives no construction).
+ *
+ * Edge (i <- j, s) exists when i, j belong to the same graph, (j,s) != (i,0) and, in float32 with
+ * every operation rounded on its own (no fused multiply-add):
+ *      t = (s1*a + s2*b) + s3*c ;  rvec = pos_i - (pos_j + t) ;  d2 = (rx*rx + ry*ry) + rz*rz < rc*rc
+ * a, b, c = rows of cell[g]. Graphs with pbc[g] == 0 (or cell == NULL) only have s = 0. For periodic
+ * graphs every image within the cutoff is found provided the atoms lie inside the cell (fractional
+ * coordinates in [0,1) up to rounding); self images (j == i, s != 0) are edges. No neighbour cap.
+ * Output order: by i, then j, then s1, s2, s3 ascending -- a destination-sorted CSR.
+ *
+ * Two calls: _count fills row_ptr and returns E; the caller allocates the edge arrays; _fill writes
+ * them. `ws` (hgnn_radius_graph_workspace_bytes) carries state from _count to _fill and must not be
+ * touched in between. `tmp` (8*E bytes) is scratch of _fill only.
+ *
+ * _count SYNCHRONISES the stream (it has to hand E to the host) and reports input errors:
+ * graph_off not starting at 0 / not non-decreasing / not ending at N -> BAD_OFFSETS; a periodic graph
+ * with |det cell| < 1e-6 A^3, or one that would need more than 127 images in a direction -> BAD_CELL;
+ * E >= 2^31 -> OVERFLOW; rc <= 0 -> BAD_SHAPE.
+ * ------------------------------------------------------------------------------------------- */
+int32_t hgnn_radius_graph_workspace_bytes(int32_t N, int32_t G, size_t* bytes_host);
+
+int32_t hgnn_radius_graph_count(void* stream, int32_t N, int32_t G,
+                                const float* pos /*[N,3]*/, const int32_t* graph_off /*[G+1]*/,
+                                const float* cell /*[G,3,3] or NULL*/, const uint8_t* pbc /*[G] or NULL*/,
+                                float rc, void* ws, size_t ws_bytes,
+                                int32_t* row_ptr /*out [N+1]*/, int64_t* E_host /*out, host*/);
+
+int32_t hgnn_radius_graph_fill(void* stream, int32_t N, int32_t G,
+                               const float* pos, const int32_t* graph_off,
+                               const float* cell, const uint8_t* pbc, float rc,
+                               void* ws, size_t ws_bytes, void* tmp, size_t tmp_bytes /*>= 8*E*/,
+                               const int32_t* row_ptr /*in [N+1]*/, int64_t E,
+                               int32_t* dst /*out [E]*/, int32_t* col /*out [E]*/,
+                               int8_t* shift /*out [E,3]*/, float* d2 /*out [E]*/,
+                               float* rvec /*out [E,3]*/, int32_t* edge_graph_ptr /*out [G+1]*/,
+                               int32_t* colT_ptr /*out [N+1]*/, int32_t* permT /*out [E]*/);
+/* colT_ptr / permT: the same edges regrouped by source atom j (edge ids ascending inside each
+ * group); the reverse pass reduces over them. edge_graph_ptr[g] = first edge of graph g. */
+
+/* ---------------------------------------------------------------------------------------------
+ * Embedding: h0[i,:] = emb[Z[i],:]  (input node features = learnable table indexed by atomic
+ * number, 0 <= Z <= HGNN_ZMAX). _bwd: g_emb[z,:] = sum over atoms with Z == z of g_h[i,:].
+ * ------------------------------------------------------------------------------------------- */
+int32_t hgnn_embed_fwd(void* stream, int32_t N, int32_t H, const int32_t* Z,
+                       const float* emb /*[ZMAX+1,H]*/, float* h /*out [N,H]*/);
+int32_t hgnn_embed_bwd(void* stream, int32_t N, int32_t H, const int32_t* Z,
+                       const float* g_h /*[N,H]*/, float* g_emb /*out [ZMAX+1,H]*/);
+
+/* ---------------------------------------------------------------------------------------------
+ * One message-passing layer of the shared stack (EGNN layer, positions held fixed):
+ *   edge  e=(i<-j): m_e = silu(W2^T silu(W1^T [h_i ; h_j ; d2_e] + b1) + b2),  x_e = wx . m_e
+ *   atom  i:        M_i = alpha * sum_{e in row i} m_e
+ *                   v'_i = v_i + alpha * sum_{e in row i} x_e * rvec_e
+ *                   h'_i = h_i + W4^T silu(W3^T [h_i ; M_i] + b3) + b4
+ * W is one flat float32 buffer, matrices row-major [in,out]:
+ *   W1[(2H+1),H] b1[H] W2[H,H] b2[H] wx[H] W3[2H,H] b3[H] W4[H,H] b4[H]     (6H^2 + 6H floats)
+ * gW of _bwd has the same layout. `saved` (size from the workspace query) is written by _fwd and
+ * read by _bwd of the same layer; `ws` is scratch. Rows with no edge get M_i = 0, v'_i = v_i.
+ * _bwd takes g_h_out = dL/dh', g_v_out = dL/dv' and writes g_h_in = dL/dh, g_v_in = dL/dv and gW.
+ * d2 and rvec are constants of the step (no gradient with respect to positions).
+ * h_out may not alias h_in; g_h_in may not alias g_h_out.
+ * ------------------------------------------------------------------------------------------- */
+int32_t hgnn_mp_layer_workspace_bytes(int32_t N, int64_t E, int32_t H, int32_t dtype,
+                                      size_t* ws_bytes_host, size_t* saved_bytes_host);
+
+int32_t hgnn_mp_layer_fwd(void* stream, int32_t N, int64_t E, int32_t H, int32_t dtype, float alpha,
+                          const int32_t* row_ptr, const int32_t* dst, const int32_t* col,
+                          const float* d2, const float* rvec,
+                          const float* h_in /*[N,H]*/, const float* v_in /*[N,3]*/,
+                          const float* W, float* h_out /*[N,H]*/, float* v_out /*[N,3]*/,
+                          void* saved, size_t saved_bytes, void* ws, size_t ws_bytes);
+
+int32_t hgnn_mp_layer_bwd(void* stream, int32_t N, int64_t E, int32_t H, int32_t dtype, float alpha,
+                          const int32_t* row_ptr, const int32_t* dst, const int32_t* col,
+                          const float* d2, const float* rvec,
+                          const int32_t* colT_ptr, const int32_t* permT,
+                          const float* h_in, const float* W, const void* saved, size_t saved_bytes,
+                          const float* g_h_out /*[N,H]*/, const float* g_v_out /*[N,3]*/,
+                          float* g_h_in /*out [N,H]*/, float* g_v_in /*out [N,3]*/,
+                          float* gW /*out, layout of W*/, void* ws, size_t ws_bytes);
+
+/* ---------------------------------------------------------------------------------------------
+ * Pooling over the contiguous atoms of each graph: p_g = sum or mean of h_i (mean gives the
+ * "energy per atom" target of the paper its per-atom normalisation). Empty graphs give 0.
+ * _bwd: g_h_i (+)= g_p[g(i)] (/ n_g);  accumulate != 0 adds into g_h instead of overwriting it.
+ * ------------------------------------------------------------------------------------------- */
+int32_t hgnn_pool_by_graph_fwd(void* stream, int32_t N, int32_t G, int32_t H, int32_t mode,
+                               const int32_t* graph_off, const float* h, float* p /*out [G,H]*/);
+int32_t hgnn_pool_by_graph_bwd(void* stream, int32_t N, int32_t G, int32_t H, int32_t mode,
+                               const int32_t* graph_off, const float* g_p, float* g_h /*[N,H]*/,
+                               int32_t accumulate);
+
+/* ---------------------------------------------------------------------------------------------
+ * Two-level multi-task decoder, all S branches resident on this GPU. Graph g is decoded by branch
+ * s = source_id[g] and by no other ("the forward propagation of an MTL output head does not
+ * require coordination with the other output heads"):
+ *   e_g = We2_s . silu(We1_s^T p_g + be1_s) + be2_s                       (energy per atom)
+ *   q_i = Wf2_s . silu(Wf1_s^T h_i + bf1_s) + bf2_s ,  F_i = q_i * v_i     (atomic force)
+ * Whead: S branches back to back, each  We1[H,Hh] be1[Hh] We2[Hh] be2[1] Wf1[H,Hh] bf1[Hh] Wf2[Hh]
+ * bf2[1]. gWhead has the same layout; a branch with no graph in the batch gets exactly zero.
+ *
+ * hgnn_multihead_plan groups graphs and their atoms by source (stable): plan is an int32 array of
+ * hgnn_multihead_plan_ints(N,G,S) entries laid out as
+ *   grp_graph_ptr[S+1] | graph_perm[G] | grp_atom_ptr[S+1] | atom_perm[N] | atom_graph[N] | internal
+ * It SYNCHRONISES the stream and returns BAD_SOURCE_ID if some source_id is outside [0,S).
+ * ------------------------------------------------------------------------------------------- */
+int64_t hgnn_multihead_plan_ints(int32_t N, int32_t G, int32_t S);
+int32_t hgnn_multihead_plan(void* stream, int32_t N, int32_t G, int32_t S,
+                            const int32_t* graph_off, const int32_t* source_id,
+                            int32_t* plan /*out*/);
+
+int32_t hgnn_multihead_decode_workspace_bytes(int32_t N, int32_t G, int32_t H, int32_t Hh, int32_t S,
+                                              int32_t dtype, size_t* ws_bytes_host,
+                                              size_t* saved_bytes_host);
+
+int32_t hgnn_multihead_decode_fwd(void* stream, int32_t N, int32_t G, int32_t H, int32_t Hh, int32_t S,
+                                  int32_t dtype, const int32_t* plan,
+                                  const float* p /*[G,H]*/, const float* h /*[N,H]*/,
+                                  const float* v /*[N,3]*/, const float* Whead,
+                                  float* energy /*out [G]*/, float* force /*out [N,3]*/,
+                                  void* saved, size_t saved_bytes, void* ws, size_t ws_bytes);
+
+int32_t hgnn_multihead_decode_bwd(void* stream, int32_t N, int32_t G, int32_t H, int32_t Hh, int32_t S,
+                                  int32_t dtype, const int32_t* plan,
+                                  const float* p, const float* h, const float* v, const float* Whead,
+                                  const void* saved, size_t saved_bytes,
+                                  const float* g_energy /*[G]*/, const float* g_force /*[N,3]*/,
+                                  float* g_p /*out [G,H]*/, float* g_h /*out [N,H]*/,
+                                  float* g_v /*out [N,3]*/, float* gWhead /*out*/,
+                                  void* ws, size_t ws_bytes);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HGNN_H */

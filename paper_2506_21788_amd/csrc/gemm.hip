@@ -1,0 +1,495 @@
+// Matrix-core kernels for gfx950 (wave64, MFMA):
+//   k_pack    fp32 [in,out] weight slices -> blocks in B-operand order (bf16 or fp32)
+//   k_gemm    row tile x (H x H) blocks, A staged through padded LDS, B streamed from L2 in operand
+//             order, epilogue (bias / SiLU' / residual adds) applied on the accumulator registers
+//   k_wgrad   sum over rows of outer products with split-K partials reduced in a fixed order
+//   k_colsum  column sums with the same deterministic two-stage reduction
+//
+// Operand layouts used below (v_mfma_f32_32x32x16_bf16 and v_mfma_f32_32x32x2_f32):
+//   A: lane l holds row (l & 31); bf16: 8 consecutive k at 8*(l>>5); fp32: the single k = (l>>5)
+//   B: lane l holds column (l & 31), same k as A
+//   D: register v of lane l is element (row 8*(v>>2) + 4*(l>>5) + (v&3), column (l & 31))
+// For fp32 the k index inside a block of 8 is permuted (lane half g takes k = 4g..4g+3 over four
+// consecutive instructions) so that both operands are fetched as one float4; the permutation is the
+// same for A and B and therefore cancels.
+#include "devmath.h"
+#include "gemm.h"
+
+namespace hgnn {
+
+// ---------------------------------------------------------------------------------------------
+// pack
+// ---------------------------------------------------------------------------------------------
+template <bool BF16>
+__global__ void k_pack(PackArgs a, int H, long src_grp_stride, long dst_grp_stride) {
+  const int b = blockIdx.y;
+  const int grp = blockIdx.z;
+  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= H * H) return;
+  const PackDesc d = a.d[b];
+  const float* src = a.src + grp * src_grp_stride + d.src_off;
+  int n, k;
+  if (BF16) {
+    const int t = idx & 7, lane = (idx >> 3) & 63, kb = (idx >> 9) % (H / 16), nb = (idx >> 9) / (H / 16);
+    n = nb * 32 + (lane & 31);
+    k = kb * 16 + (lane >> 5) * 8 + t;
+  } else {
+    const int t = idx & 3, lane = (idx >> 2) & 63, kb = (idx >> 8) % (H / 8), nb = (idx >> 8) / (H / 8);
+    n = nb * 32 + (lane & 31);
+    k = kb * 8 + (lane >> 5) * 4 + t;
+  }
+  const float v = src[(long)k * d.sk + (long)n * d.sn];
+  const long o = grp * dst_grp_stride + (long)b * H * H + idx;
+  if (BF16) {
+    reinterpret_cast<unsigned short*>(a.dst)[o] = (unsigned short)f2bf_bits(v);
+  } else {
+    reinterpret_cast<float*>(a.dst)[o] = v;
+  }
+}
+
+int32_t launch_pack(hipStream_t st, int H, bool bf16, const PackArgs& a, int groups, long src_grp_stride,
+                    long dst_grp_stride_elems) {
+  if (a.nblocks <= 0 || groups <= 0) return HGNN_OK;
+  dim3 grid((H * H + 255) / 256, a.nblocks, groups);
+  if (bf16) k_pack<true><<<grid, 256, 0, st>>>(a, H, src_grp_stride, dst_grp_stride_elems);
+  else k_pack<false><<<grid, 256, 0, st>>>(a, H, src_grp_stride, dst_grp_stride_elems);
+  HGNN_LAUNCH_CHECK("k_pack");
+  return HGNN_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// row-tile GEMM
+// ---------------------------------------------------------------------------------------------
+template <int H, bool BF16>
+struct GemmCfg {
+  static constexpr int TM = BF16 ? 128 : (H == 256 ? 64 : 128);
+  static constexpr int WC = (H / 32 < 4) ? H / 32 : 4;   // wavefronts side by side over columns
+  static constexpr int WR = 4 / WC;                      // and over rows
+  static constexpr int WROWS = TM / WR;
+  static constexpr int WCOLS = H / WC;
+  static constexpr int RB = WROWS / 32;
+  static constexpr int CB = WCOLS / 32;
+  static constexpr int STRIDE = BF16 ? H + 8 : H + 4;    // LDS row pitch in elements (bank spread)
+  static constexpr size_t LDS_BYTES = (size_t)TM * STRIDE * (BF16 ? 2 : 4);
+};
+
+__device__ __forceinline__ bool tile_of_group(const int32_t* grp_ptr, int S, int TM, int tile, int& grp, int& rbeg,
+                                              int& rend) {
+  for (int s = 0; s < S; ++s) {
+    const int b = grp_ptr[s], e = grp_ptr[s + 1];
+    const int nt = (e - b + TM - 1) / TM;
+    if (tile < nt) {
+      grp = s;
+      rbeg = b + tile * TM;
+      rend = e;
+      return true;
+    }
+    tile -= nt;
+  }
+  return false;
+}
+
+template <int H, bool BF16>
+__global__ void __launch_bounds__(256) k_gemm(GemmArgs p) {
+  using C = GemmCfg<H, BF16>;
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wr = wave / C::WC, wc = wave % C::WC;
+  const int cb = blockIdx.y;
+  int grp = 0, rbeg, rend;
+  if (p.grp_ptr) {
+    if (!tile_of_group(p.grp_ptr, p.S, C::TM, blockIdx.x, grp, rbeg, rend)) return;
+  } else {
+    rbeg = blockIdx.x * C::TM;
+    rend = p.M;
+    if (rbeg >= rend) return;
+  }
+
+  f32x16_t acc[C::RB][C::CB];
+#pragma unroll
+  for (int i = 0; i < C::RB; ++i)
+#pragma unroll
+    for (int j = 0; j < C::CB; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  for (int kc = 0; kc < p.nkc; ++kc) {
+    if (kc) __syncthreads();
+    // ---- stage the A tile (rows rbeg.., all H columns of chunk kc) into LDS
+    const float* __restrict__ A = p.A[kc];
+    const int lda = p.lda[kc];
+    constexpr int CH = H / 4;
+    for (int c = tid; c < C::TM * CH; c += 256) {
+      const int r = c / CH, q = c - r * CH;
+      const int pos = rbeg + r;
+      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (pos < rend) {
+        const long gr = p.row_idx ? p.row_idx[pos] : pos;
+        v = *reinterpret_cast<const float4*>(A + gr * lda + q * 4);
+        if (p.a_silu) {
+          v.x = silu_f(v.x); v.y = silu_f(v.y); v.z = silu_f(v.z); v.w = silu_f(v.w);
+        }
+      }
+      if (BF16) {
+        uint2 w;
+        w.x = pack_bf16x2(v.x, v.y);
+        w.y = pack_bf16x2(v.z, v.w);
+        *reinterpret_cast<uint2*>(smem + ((size_t)r * C::STRIDE + q * 4) * 2) = w;
+      } else {
+        *reinterpret_cast<float4*>(smem + ((size_t)r * C::STRIDE + q * 4) * 4) = v;
+      }
+    }
+    __syncthreads();
+    // ---- multiply
+    const long bblk0 = grp * p.grp_blk_stride + p.blk[kc][cb];
+    if (BF16) {
+      const bf16x8_t* __restrict__ Bp = reinterpret_cast<const bf16x8_t*>(p.B) + bblk0 * (H * H / 8);
+      constexpr int NKB = H / 16;
+#pragma unroll 4
+      for (int kb = 0; kb < NKB; ++kb) {
+        bf16x8_t a[C::RB];
+#pragma unroll
+        for (int i = 0; i < C::RB; ++i) {
+          const int row = wr * C::WROWS + i * 32 + (lane & 31);
+          a[i] = *reinterpret_cast<const bf16x8_t*>(smem + ((size_t)row * C::STRIDE + kb * 16 + (lane >> 5) * 8) * 2);
+        }
+#pragma unroll
+        for (int j = 0; j < C::CB; ++j) {
+          const int nb = wc * C::CB + j;
+          const bf16x8_t b = Bp[(nb * NKB + kb) * 64 + lane];
+#pragma unroll
+          for (int i = 0; i < C::RB; ++i)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b, acc[i][j], 0, 0, 0);
+        }
+      }
+    } else {
+      const float4* __restrict__ Bp = reinterpret_cast<const float4*>(p.B) + bblk0 * (H * H / 4);
+      constexpr int NKB = H / 8;
+#pragma unroll 4
+      for (int kb = 0; kb < NKB; ++kb) {
+        float4 a[C::RB];
+#pragma unroll
+        for (int i = 0; i < C::RB; ++i) {
+          const int row = wr * C::WROWS + i * 32 + (lane & 31);
+          a[i] = *reinterpret_cast<const float4*>(smem + ((size_t)row * C::STRIDE + kb * 8 + (lane >> 5) * 4) * 4);
+        }
+#pragma unroll
+        for (int j = 0; j < C::CB; ++j) {
+          const int nb = wc * C::CB + j;
+          const float4 b = Bp[(nb * NKB + kb) * 64 + lane];
+#pragma unroll
+          for (int i = 0; i < C::RB; ++i) {
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].x, b.x, acc[i][j], 0, 0, 0);
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].y, b.y, acc[i][j], 0, 0, 0);
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].z, b.z, acc[i][j], 0, 0, 0);
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].w, b.w, acc[i][j], 0, 0, 0);
+          }
+        }
+      }
+    }
+  }
+
+  // ---- epilogue on the accumulator registers
+  const bool use_bias = p.bias && ((p.bias_cb_mask >> cb) & 1);
+#pragma unroll
+  for (int j = 0; j < C::CB; ++j) {
+    const int col = wc * C::WCOLS + j * 32 + (lane & 31);
+    const int gcol = cb * H + col;
+    const float bv = use_bias ? p.bias[grp * p.grp_bias_stride + col] : 0.f;
+#pragma unroll
+    for (int i = 0; i < C::RB; ++i) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int r = wr * C::WROWS + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+        const int pos = rbeg + r;
+        if (pos < rend) {
+          const long gr = p.row_idx ? p.row_idx[pos] : pos;
+          float x = acc[i][j][v] + bv;
+          if (p.mul) {
+            const float mval = p.mul[gr * p.ldmul + gcol];
+            x *= p.mul_is_z ? dsilu_f(mval) : mval;
+          }
+          if (p.add1) x += p.add1[gr * p.ldadd1 + gcol];
+          if (p.add2) x += p.add2[gr * p.ldadd2 + gcol];
+          p.C[gr * p.ldc + gcol] = x;
+        }
+      }
+    }
+  }
+}
+
+template <int H, bool BF16>
+static int32_t launch_gemm_t(hipStream_t st, const GemmArgs& a) {
+  using C = GemmCfg<H, BF16>;
+  if (a.M <= 0) return HGNN_OK;
+  const int tiles = (a.M + C::TM - 1) / C::TM + (a.grp_ptr ? a.S : 0);
+  static bool attr_set = false;
+  if (!attr_set) {
+    HGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<H, BF16>),
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES));
+    attr_set = true;
+  }
+  k_gemm<H, BF16><<<dim3(tiles, a.ncb), 256, C::LDS_BYTES, st>>>(a);
+  HGNN_LAUNCH_CHECK("k_gemm");
+  return HGNN_OK;
+}
+
+int32_t launch_gemm(hipStream_t st, int H, bool bf16, const GemmArgs& a) {
+  HGNN_REQUIRE(a.nkc >= 1 && a.nkc <= 2 && a.ncb >= 1 && a.ncb <= 2, HGNN_ERR_BAD_SHAPE, "gemm: bad chunk counts");
+  HGNN_REQUIRE(a.A[0] && a.B && a.C, HGNN_ERR_NULLPTR, "gemm: null operand");
+  switch (H) {
+    case 64: return bf16 ? launch_gemm_t<64, true>(st, a) : launch_gemm_t<64, false>(st, a);
+    case 128: return bf16 ? launch_gemm_t<128, true>(st, a) : launch_gemm_t<128, false>(st, a);
+    case 256: return bf16 ? launch_gemm_t<256, true>(st, a) : launch_gemm_t<256, false>(st, a);
+  }
+  return set_error(HGNN_ERR_BAD_SHAPE, "H must be 64, 128 or 256 (got %d)", H);
+}
+
+// ---------------------------------------------------------------------------------------------
+// deterministic reduction of split partials:  dest[blk][i] = sum_s partial[grp][s][blk][i]
+// ---------------------------------------------------------------------------------------------
+struct ReduceArgs {
+  const float* partial;
+  int nsplit;
+  int nblk;
+  long blk_elems;
+  float* dest[4];
+  long grp_dest_stride;
+};
+
+__global__ void k_reduce_partials(ReduceArgs a) {
+  const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  const int blk = blockIdx.y, grp = blockIdx.z;
+  if (i >= a.blk_elems) return;
+  const float* p = a.partial + ((long)grp * a.nsplit * a.nblk + blk) * a.blk_elems + i;
+  const long step = (long)a.nblk * a.blk_elems;
+  float s = 0.f;
+  for (int k = 0; k < a.nsplit; ++k) s += p[k * step];
+  a.dest[blk][grp * a.grp_dest_stride + i] = s;
+}
+
+// ---------------------------------------------------------------------------------------------
+// transposed GEMM
+// ---------------------------------------------------------------------------------------------
+constexpr int WG_RC = 32;  // rows staged per step
+
+template <int H>
+struct WgradCfg {
+  static constexpr int OT = H < 128 ? H : 128;  // output tile edge
+  static constexpr int WT = OT / 2;             // per-wave edge (2 x 2 wavefronts)
+  static constexpr int NB = WT / 32;
+  static constexpr int STRIDE = OT + 4;
+  static constexpr int TILES = H / OT;
+};
+
+template <int H, bool BF16>
+__global__ void __launch_bounds__(256) k_wgrad(WgradArgs p, int nsplit, int rows_per_split) {
+  using C = WgradCfg<H>;
+  __shared__ __align__(16) float sA[WG_RC * C::STRIDE];
+  __shared__ __align__(16) float sB[WG_RC * C::STRIDE];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wa = wave >> 1, wb = wave & 1;
+  const int split = blockIdx.x, grp = blockIdx.z;
+  int y = blockIdx.y;
+  const int tb = y % C::TILES; y /= C::TILES;
+  const int ta = y % C::TILES; y /= C::TILES;
+  const int ib = y % p.nB;
+  const int ia = y / p.nB;
+  const int blkid = ia * p.nB + ib;
+  long gbeg = 0, gend = p.M;
+  if (p.grp_ptr) { gbeg = p.grp_ptr[grp]; gend = p.grp_ptr[grp + 1]; }
+  long rbeg = gbeg + (long)split * rows_per_split;
+  long rend = rbeg + rows_per_split;
+  if (rend > gend) rend = gend;
+
+  f32x16_t acc[C::NB][C::NB];
+#pragma unroll
+  for (int i = 0; i < C::NB; ++i)
+#pragma unroll
+    for (int j = 0; j < C::NB; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  const float* __restrict__ A = p.A[ia];
+  const float* __restrict__ B = p.B[ib];
+  const int lda = p.lda[ia], ldb = p.ldb[ib];
+  constexpr int CH = C::OT / 4;
+  for (long r0 = rbeg; r0 < rend; r0 += WG_RC) {
+    __syncthreads();
+    for (int c = tid; c < WG_RC * CH; c += 256) {
+      const int r = c / CH, q = c - r * CH;
+      float4 va = make_float4(0.f, 0.f, 0.f, 0.f), vb = va;
+      if (r0 + r < rend) {
+        const long gr = p.row_idx ? p.row_idx[r0 + r] : (r0 + r);
+        va = *reinterpret_cast<const float4*>(A + gr * lda + ta * C::OT + q * 4);
+        vb = *reinterpret_cast<const float4*>(B + gr * ldb + tb * C::OT + q * 4);
+        if (p.a_silu) { va.x = silu_f(va.x); va.y = silu_f(va.y); va.z = silu_f(va.z); va.w = silu_f(va.w); }
+      }
+      *reinterpret_cast<float4*>(&sA[r * C::STRIDE + q * 4]) = va;
+      *reinterpret_cast<float4*>(&sB[r * C::STRIDE + q * 4]) = vb;
+    }
+    __syncthreads();
+    if (BF16) {
+#pragma unroll
+      for (int ks = 0; ks < WG_RC / 16; ++ks) {
+        const int rr = ks * 16 + (lane >> 5) * 8;
+        bf16x8_t a[C::NB], b[C::NB];
+#pragma unroll
+        for (int i = 0; i < C::NB; ++i) {
+          const int ca = wa * C::WT + i * 32 + (lane & 31);
+          const int cbb = wb * C::WT + i * 32 + (lane & 31);
+          unsigned ua[4], ub[4];
+#pragma unroll
+          for (int t = 0; t < 4; ++t) {
+            ua[t] = pack_bf16x2(sA[(rr + 2 * t) * C::STRIDE + ca], sA[(rr + 2 * t + 1) * C::STRIDE + ca]);
+            ub[t] = pack_bf16x2(sB[(rr + 2 * t) * C::STRIDE + cbb], sB[(rr + 2 * t + 1) * C::STRIDE + cbb]);
+          }
+          uint4 pa = make_uint4(ua[0], ua[1], ua[2], ua[3]);
+          uint4 pb = make_uint4(ub[0], ub[1], ub[2], ub[3]);
+          a[i] = *reinterpret_cast<bf16x8_t*>(&pa);
+          b[i] = *reinterpret_cast<bf16x8_t*>(&pb);
+        }
+#pragma unroll
+        for (int i = 0; i < C::NB; ++i)
+#pragma unroll
+          for (int j = 0; j < C::NB; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+      }
+    } else {
+#pragma unroll
+      for (int ks = 0; ks < WG_RC / 2; ++ks) {
+        const int rr = ks * 2 + (lane >> 5);
+        float a[C::NB], b[C::NB];
+#pragma unroll
+        for (int i = 0; i < C::NB; ++i) {
+          a[i] = sA[rr * C::STRIDE + wa * C::WT + i * 32 + (lane & 31)];
+          b[i] = sB[rr * C::STRIDE + wb * C::WT + i * 32 + (lane & 31)];
+        }
+#pragma unroll
+        for (int i = 0; i < C::NB; ++i)
+#pragma unroll
+          for (int j = 0; j < C::NB; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
+      }
+    }
+  }
+  const int nblk = p.nA * p.nB;
+  float* out = p.partial + (((long)grp * nsplit + split) * nblk + blkid) * (long)(H * H);
+#pragma unroll
+  for (int i = 0; i < C::NB; ++i)
+#pragma unroll
+    for (int j = 0; j < C::NB; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int k1 = ta * C::OT + wa * C::WT + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+        const int k2 = tb * C::OT + wb * C::WT + j * 32 + (lane & 31);
+        out[k1 * H + k2] = acc[i][j][v];
+      }
+}
+
+int wgrad_splits(int64_t M) {
+  int64_t s = (M + 4095) / 4096;
+  if (s < 1) s = 1;
+  if (s > 192) s = 192;
+  return (int)s;
+}
+
+size_t wgrad_partial_floats(int H, int64_t M, int nblocks, int S) {
+  return (size_t)wgrad_splits(M) * nblocks * S * H * H;
+}
+
+template <int H, bool BF16>
+static int32_t launch_wgrad_t(hipStream_t st, const WgradArgs& a) {
+  using C = WgradCfg<H>;
+  const int nsplit = wgrad_splits(a.M);
+  int64_t rps = (a.M + nsplit - 1) / nsplit;
+  rps = (rps + WG_RC - 1) / WG_RC * WG_RC;
+  if (rps < WG_RC) rps = WG_RC;
+  const int nblk = a.nA * a.nB;
+  const int groups = a.grp_ptr ? a.S : 1;
+  k_wgrad<H, BF16><<<dim3(nsplit, nblk * C::TILES * C::TILES, groups), 256, 0, st>>>(a, nsplit, (int)rps);
+  HGNN_LAUNCH_CHECK("k_wgrad");
+  ReduceArgs r;
+  r.partial = a.partial;
+  r.nsplit = nsplit;
+  r.nblk = nblk;
+  r.blk_elems = (long)H * H;
+  for (int i = 0; i < 4; ++i) r.dest[i] = a.dest[i];
+  r.grp_dest_stride = a.grp_dest_stride;
+  k_reduce_partials<<<dim3((H * H + 255) / 256, nblk, groups), 256, 0, st>>>(r);
+  HGNN_LAUNCH_CHECK("k_reduce_partials");
+  return HGNN_OK;
+}
+
+int32_t launch_wgrad(hipStream_t st, int H, bool bf16, const WgradArgs& a) {
+  HGNN_REQUIRE(a.nA >= 1 && a.nB >= 1 && a.nA * a.nB <= 4, HGNN_ERR_BAD_SHAPE, "wgrad: bad block counts");
+  HGNN_REQUIRE(a.A[0] && a.B[0] && a.partial && a.dest[0], HGNN_ERR_NULLPTR, "wgrad: null operand");
+  switch (H) {
+    case 64: return bf16 ? launch_wgrad_t<64, true>(st, a) : launch_wgrad_t<64, false>(st, a);
+    case 128: return bf16 ? launch_wgrad_t<128, true>(st, a) : launch_wgrad_t<128, false>(st, a);
+    case 256: return bf16 ? launch_wgrad_t<256, true>(st, a) : launch_wgrad_t<256, false>(st, a);
+  }
+  return set_error(HGNN_ERR_BAD_SHAPE, "H must be 64, 128 or 256 (got %d)", H);
+}
+
+// ---------------------------------------------------------------------------------------------
+// column sums
+// ---------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) k_colsum(ColsumArgs p, int H, int nsplit, int rows_per_split) {
+  __shared__ float sh[256];
+  const int tid = threadIdx.x;
+  const int c = tid % H, ph = tid / H, nph = 256 / H;
+  const int split = blockIdx.x, grp = blockIdx.y;
+  long gbeg = 0, gend = p.M;
+  if (p.grp_ptr) { gbeg = p.grp_ptr[grp]; gend = p.grp_ptr[grp + 1]; }
+  long rbeg = gbeg + (long)split * rows_per_split;
+  long rend = rbeg + rows_per_split;
+  if (rend > gend) rend = gend;
+  float s = 0.f;
+  for (long r = rbeg + ph; r < rend; r += nph) {
+    const long gr = p.row_idx ? p.row_idx[r] : r;
+    float x = p.X[gr * p.ldx + c];
+    if (p.f_silu) x = silu_f(x);
+    if (p.w) x *= p.w[gr];
+    s += x;
+  }
+  sh[tid] = s;
+  __syncthreads();
+  if (ph == 0) {
+    for (int k = 1; k < nph; ++k) s += sh[k * H + c];
+    p.partial[((long)grp * nsplit + split) * H + c] = s;
+  }
+}
+
+static int colsum_splits(int64_t M) {
+  int64_t s = (M + 1023) / 1024;
+  if (s < 1) s = 1;
+  if (s > 512) s = 512;
+  return (int)s;
+}
+
+size_t colsum_partial_floats(int H, int64_t M, int S) { return (size_t)colsum_splits(M) * S * H; }
+
+int32_t launch_colsum(hipStream_t st, int H, const ColsumArgs& a) {
+  HGNN_REQUIRE(a.X && a.dest && a.partial, HGNN_ERR_NULLPTR, "colsum: null operand");
+  HGNN_REQUIRE(valid_H(H), HGNN_ERR_BAD_SHAPE, "H must be 64, 128 or 256 (got %d)", H);
+  const int nsplit = colsum_splits(a.M);
+  int64_t rps = (a.M + nsplit - 1) / nsplit;
+  if (rps < 1) rps = 1;
+  const int groups = a.grp_ptr ? a.S : 1;
+  k_colsum<<<dim3(nsplit, groups), 256, 0, st>>>(a, H, nsplit, (int)rps);
+  HGNN_LAUNCH_CHECK("k_colsum");
+  ReduceArgs r;
+  r.partial = a.partial;
+  r.nsplit = nsplit;
+  r.nblk = 1;
+  r.blk_elems = H;
+  r.dest[0] = a.dest;
+  r.dest[1] = r.dest[2] = r.dest[3] = nullptr;
+  r.grp_dest_stride = a.grp_dest_stride;
+  k_reduce_partials<<<dim3((H + 255) / 256, 1, groups), 256, 0, st>>>(r);
+  HGNN_LAUNCH_CHECK("k_reduce_partials");
+  return HGNN_OK;
+}
+
+}  // namespace hgnn

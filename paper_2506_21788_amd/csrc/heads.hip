@@ -1,0 +1,548 @@
+// Embedding, pooling, routing plan and the per-source decoding heads (grouped GEMMs: one weight set
+// per source, rows of each source made contiguous through the plan's permutations).
+#include "devmath.h"
+#include "edgeops.h"
+#include "gemm.h"
+
+namespace hgnn {
+
+static inline unsigned nb64(int64_t n, int t) { return (unsigned)((n + t - 1) / t); }
+
+__device__ inline int find_graph_of_atom(const int32_t* __restrict__ graph_off, int G, int i) {
+  int lo = 0, hi = G - 1;
+  while (lo < hi) {
+    int mid = (lo + hi) >> 1;
+    if (graph_off[mid + 1] > i) hi = mid; else lo = mid + 1;
+  }
+  return lo;
+}
+
+// ---------------------------------------------------------------------------------------------
+// embedding
+// ---------------------------------------------------------------------------------------------
+__global__ void k_embed_fwd(int N, int H, const int32_t* __restrict__ Z, const float* __restrict__ emb,
+                            float* __restrict__ h) {
+  const int CH = H >> 2;
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (int64_t)N * CH) return;
+  const int64_t i = idx / CH;
+  const int q = (int)(idx - i * CH);
+  int z = Z[i];
+  z = z < 0 ? 0 : (z > HGNN_ZMAX ? HGNN_ZMAX : z);
+  *reinterpret_cast<float4*>(h + i * H + q * 4) = *reinterpret_cast<const float4*>(emb + (long)z * H + q * 4);
+}
+
+// one block per table row z: fixed-order sum over the atoms with Z == z
+__global__ void __launch_bounds__(256)
+k_embed_bwd(int N, int H, const int32_t* __restrict__ Z, const float* __restrict__ g_h, float* __restrict__ g_emb) {
+  __shared__ float sh[256 * 4];
+  const int z = blockIdx.x;
+  const int CH = H >> 2;
+  const int q = threadIdx.x % CH, ph = threadIdx.x / CH, nph = 256 / CH;
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int i = ph; i < N; i += nph) {
+    if (Z[i] == z) {
+      const float4 v = *reinterpret_cast<const float4*>(g_h + (size_t)i * H + q * 4);
+      acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+    }
+  }
+  reinterpret_cast<float4*>(sh)[threadIdx.x] = acc;
+  __syncthreads();
+  if (ph == 0) {
+    for (int k = 1; k < nph; ++k) {
+      const float4 v = reinterpret_cast<float4*>(sh)[k * CH + q];
+      acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+    }
+    *reinterpret_cast<float4*>(g_emb + (size_t)z * H + q * 4) = acc;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// pooling
+// ---------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(1024)
+k_pool_fwd(int H, int mode, const int32_t* __restrict__ graph_off, const float* __restrict__ h, float* __restrict__ p) {
+  __shared__ float sh[1024 * 4];
+  const int g = blockIdx.x;
+  const int CH = H >> 2;
+  const int q = threadIdx.x % CH, ph = threadIdx.x / CH, nph = 1024 / CH;
+  const int lo = graph_off[g], hi = graph_off[g + 1];
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int i = lo + ph; i < hi; i += nph) {
+    const float4 v = *reinterpret_cast<const float4*>(h + (size_t)i * H + q * 4);
+    acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+  }
+  reinterpret_cast<float4*>(sh)[threadIdx.x] = acc;
+  __syncthreads();
+  if (ph == 0) {
+    for (int k = 1; k < nph; ++k) {
+      const float4 v = reinterpret_cast<float4*>(sh)[k * CH + q];
+      acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+    }
+    const float sc = (mode == HGNN_POOL_MEAN && hi > lo) ? 1.0f / (float)(hi - lo) : 1.0f;
+    *reinterpret_cast<float4*>(p + (size_t)g * H + q * 4) = make_float4(acc.x * sc, acc.y * sc, acc.z * sc, acc.w * sc);
+  }
+}
+
+__global__ void k_pool_bwd(int N, int G, int H, int mode, const int32_t* __restrict__ graph_off,
+                           const float* __restrict__ g_p, float* __restrict__ g_h, int accumulate) {
+  const int CH = H >> 2;
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (int64_t)N * CH) return;
+  const int i = (int)(idx / CH);
+  const int q = (int)(idx - (int64_t)i * CH);
+  const int g = find_graph_of_atom(graph_off, G, i);
+  const int n = graph_off[g + 1] - graph_off[g];
+  const float sc = (mode == HGNN_POOL_MEAN) ? 1.0f / (float)n : 1.0f;
+  float4 v = *reinterpret_cast<const float4*>(g_p + (size_t)g * H + q * 4);
+  v.x *= sc; v.y *= sc; v.z *= sc; v.w *= sc;
+  float4* o = reinterpret_cast<float4*>(g_h + (size_t)i * H + q * 4);
+  if (accumulate) {
+    const float4 c = *o;
+    v.x += c.x; v.y += c.y; v.z += c.z; v.w += c.w;
+  }
+  *o = v;
+}
+
+// ---------------------------------------------------------------------------------------------
+// routing plan
+// ---------------------------------------------------------------------------------------------
+struct PlanView {
+  int32_t *grp_graph_ptr, *graph_perm, *grp_atom_ptr, *atom_perm, *atom_graph, *graph_src, *graph_dst_off, *status;
+  int64_t ints;
+};
+
+template <typename T>
+static PlanView plan_view(T* plan, int N, int G, int S) {
+  PlanView v;
+  int32_t* p = const_cast<int32_t*>(plan);
+  int64_t o = 0;
+  v.grp_graph_ptr = p + o; o += S + 1;
+  v.graph_perm = p + o; o += G;
+  v.grp_atom_ptr = p + o; o += S + 1;
+  v.atom_perm = p + o; o += N;
+  v.atom_graph = p + o; o += N;
+  v.graph_src = p + o; o += G;
+  v.graph_dst_off = p + o; o += G;
+  v.status = p + o; o += 4;
+  v.ints = o;
+  return v;
+}
+
+// one block; thread s collects the graphs of source s in ascending order (stable by construction)
+__global__ void k_plan_graphs(int G, int S, const int32_t* __restrict__ graph_off, const int32_t* __restrict__ source_id,
+                              PlanView v) {
+  __shared__ int s_cnt[1024];
+  __shared__ int s_atoms[1024];
+  if (threadIdx.x == 0) v.status[0] = 0;
+  __syncthreads();
+  // validation + copy
+  for (int g = threadIdx.x; g < G; g += blockDim.x) {
+    const int s = source_id[g];
+    v.graph_src[g] = s;
+    if (s < 0 || s >= S) atomicOr(v.status, 1);
+  }
+  __syncthreads();
+  if (v.status[0]) return;
+  for (int s0 = 0; s0 < S; s0 += blockDim.x) {
+    const int s = s0 + threadIdx.x;
+    int cnt = 0, atoms = 0;
+    if (s < S) {
+      for (int g = 0; g < G; ++g)
+        if (source_id[g] == s) { ++cnt; atoms += graph_off[g + 1] - graph_off[g]; }
+    }
+    s_cnt[threadIdx.x] = cnt;
+    s_atoms[threadIdx.x] = atoms;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      int cg = s0 == 0 ? 0 : v.grp_graph_ptr[s0];
+      int ca = s0 == 0 ? 0 : v.grp_atom_ptr[s0];
+      for (int k = 0; k < (int)blockDim.x && s0 + k < S; ++k) {
+        v.grp_graph_ptr[s0 + k] = cg;
+        v.grp_atom_ptr[s0 + k] = ca;
+        cg += s_cnt[k];
+        ca += s_atoms[k];
+      }
+      const int last = (s0 + (int)blockDim.x < S) ? s0 + (int)blockDim.x : S;
+      v.grp_graph_ptr[last] = cg;
+      v.grp_atom_ptr[last] = ca;
+    }
+    __syncthreads();
+    if (s < S) {
+      int kg = v.grp_graph_ptr[s], ka = v.grp_atom_ptr[s];
+      for (int g = 0; g < G; ++g)
+        if (source_id[g] == s) {
+          v.graph_perm[kg++] = g;
+          v.graph_dst_off[g] = ka;
+          ka += graph_off[g + 1] - graph_off[g];
+        }
+    }
+    __syncthreads();
+  }
+}
+
+__global__ void k_plan_atoms(int N, int G, const int32_t* __restrict__ graph_off, PlanView v) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= N) return;
+  const int g = find_graph_of_atom(graph_off, G, i);
+  v.atom_graph[i] = g;
+  v.atom_perm[v.graph_dst_off[g] + (i - graph_off[g])] = i;
+}
+
+// ---------------------------------------------------------------------------------------------
+// head output layers (width Hh -> 1) and their reverse
+// ---------------------------------------------------------------------------------------------
+struct HeadOff {  // element offsets inside one branch
+  long We1, be1, We2, be2, Wf1, bf1, Wf2, bf2, per;
+  HeadOff(long H, long Hh) {
+    long o = 0;
+    We1 = o; o += H * Hh;
+    be1 = o; o += Hh;
+    We2 = o; o += Hh;
+    be2 = o; o += 1;
+    Wf1 = o; o += H * Hh;
+    bf1 = o; o += Hh;
+    Wf2 = o; o += Hh;
+    bf2 = o; o += 1;
+    per = o;
+  }
+};
+
+__device__ __forceinline__ float wsum(float x) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o);
+  return x;
+}
+
+// rows 0..G-1: graphs (energy); rows G..G+N-1: atoms (force). One wavefront per row.
+__global__ void __launch_bounds__(256)
+k_head_out_fwd(int N, int G, int Hh, const float* __restrict__ ze, const float* __restrict__ zf,
+               const float* __restrict__ Whead, HeadOff o, const int32_t* __restrict__ graph_src,
+               const int32_t* __restrict__ atom_graph, const float* __restrict__ v, float* __restrict__ energy,
+               float* __restrict__ force, float* __restrict__ qsave) {
+  const int r = (int)(((size_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6);
+  const int lane = threadIdx.x & 63;
+  if (r >= G + N) return;
+  const bool is_graph = r < G;
+  const int i = is_graph ? r : r - G;
+  const int s = graph_src[is_graph ? i : atom_graph[i]];
+  const float* z = is_graph ? ze + (size_t)i * Hh : zf + (size_t)i * Hh;
+  const float* w2 = Whead + s * o.per + (is_graph ? o.We2 : o.Wf2);
+  float acc = 0.f;
+  for (int c = lane; c < Hh; c += 64) acc += w2[c] * silu_f(z[c]);
+  acc = wsum(acc);
+  if (lane == 0) {
+    const float out = acc + Whead[s * o.per + (is_graph ? o.be2 : o.bf2)];
+    if (is_graph) {
+      energy[i] = out;
+    } else {
+      qsave[i] = out;
+      force[3 * (size_t)i] = out * v[3 * (size_t)i];
+      force[3 * (size_t)i + 1] = out * v[3 * (size_t)i + 1];
+      force[3 * (size_t)i + 2] = out * v[3 * (size_t)i + 2];
+    }
+  }
+}
+
+// g_z = g_out * W2 * silu'(z); also g_v = q * g_force, and the per-row scalar g_out (gq / copy of gE)
+__global__ void __launch_bounds__(256)
+k_head_out_bwd(int N, int G, int Hh, const float* __restrict__ ze, const float* __restrict__ zf,
+               const float* __restrict__ Whead, HeadOff o, const int32_t* __restrict__ graph_src,
+               const int32_t* __restrict__ atom_graph, const float* __restrict__ v, const float* __restrict__ qsave,
+               const float* __restrict__ g_energy, const float* __restrict__ g_force, float* __restrict__ g_ze,
+               float* __restrict__ g_zf, float* __restrict__ gq, float* __restrict__ g_v) {
+  const int r = (int)(((size_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6);
+  const int lane = threadIdx.x & 63;
+  if (r >= G + N) return;
+  const bool is_graph = r < G;
+  const int i = is_graph ? r : r - G;
+  const int s = graph_src[is_graph ? i : atom_graph[i]];
+  float go;
+  if (is_graph) {
+    go = g_energy[i];
+  } else {
+    const float gx = g_force[3 * (size_t)i], gy = g_force[3 * (size_t)i + 1], gz = g_force[3 * (size_t)i + 2];
+    go = gx * v[3 * (size_t)i] + gy * v[3 * (size_t)i + 1] + gz * v[3 * (size_t)i + 2];
+    if (lane == 0) {
+      const float q = qsave[i];
+      gq[i] = go;
+      g_v[3 * (size_t)i] = q * gx;
+      g_v[3 * (size_t)i + 1] = q * gy;
+      g_v[3 * (size_t)i + 2] = q * gz;
+    }
+  }
+  const float* z = is_graph ? ze + (size_t)i * Hh : zf + (size_t)i * Hh;
+  float* gz_ = is_graph ? g_ze + (size_t)i * Hh : g_zf + (size_t)i * Hh;
+  const float* w2 = Whead + s * o.per + (is_graph ? o.We2 : o.Wf2);
+  for (int c = lane; c < Hh; c += 64) gz_[c] = go * w2[c] * dsilu_f(z[c]);
+}
+
+// dest[s*stride] = sum over positions of group s of w[row_idx[pos]]   (one wavefront per group)
+__global__ void k_group_scalar_sum(const float* __restrict__ w, const int32_t* __restrict__ row_idx,
+                                   const int32_t* __restrict__ grp_ptr, float* __restrict__ dest, long stride) {
+  const int s = blockIdx.x;
+  const int lane = threadIdx.x;
+  float acc = 0.f;
+  for (int t = grp_ptr[s] + lane; t < grp_ptr[s + 1]; t += 64) acc += w[row_idx[t]];
+  acc = wsum(acc);
+  if (lane == 0) dest[s * stride] = acc;
+}
+
+struct HeadSaved {
+  float *ze, *zf, *q;
+  size_t bytes;
+};
+static HeadSaved carve_head_saved(void* p, int N, int G, int Hh) {
+  Carver c(p);
+  HeadSaved s;
+  s.ze = c.take<float>((size_t)G * Hh);
+  s.zf = c.take<float>((size_t)N * Hh);
+  s.q = c.take<float>((size_t)N + 1);
+  s.bytes = c.used();
+  return s;
+}
+struct HeadWs {
+  void* packed;  // [S][2] blocks
+  float *g_ze, *g_zf, *gq, *partial;
+  size_t bytes;
+};
+static HeadWs carve_head_ws(void* p, int N, int G, int H, int Hh, int S, bool bf16) {
+  Carver c(p);
+  HeadWs w;
+  w.packed = c.take<char>((size_t)S * 2 * packed_block_bytes(H, bf16));
+  w.g_ze = c.take<float>((size_t)G * Hh);
+  w.g_zf = c.take<float>((size_t)N * Hh);
+  w.gq = c.take<float>((size_t)N + 1);
+  const int64_t mx = N > G ? N : G;
+  size_t pf = wgrad_partial_floats(H, mx, 1, S);
+  size_t cf = colsum_partial_floats(H, mx, S);
+  w.partial = c.take<float>(pf > cf ? pf : cf);
+  w.bytes = c.used();
+  return w;
+}
+
+static int32_t check_head_args(int N, int G, int H, int Hh, int S, int dtype) {
+  HGNN_REQUIRE(N >= 0 && G >= 0, HGNN_ERR_BAD_SHAPE, "negative N or G");
+  HGNN_REQUIRE(S >= 1 && S <= 65535, HGNN_ERR_BAD_SHAPE, "S must be in 1..65535 (got %d)", S);
+  HGNN_REQUIRE(valid_H(H), HGNN_ERR_BAD_SHAPE, "H must be 64, 128 or 256 (got %d)", H);
+  HGNN_REQUIRE(Hh == H, HGNN_ERR_BAD_SHAPE, "head width Hh must equal H (got %d vs %d)", Hh, H);
+  HGNN_REQUIRE(dtype == HGNN_F32 || dtype == HGNN_BF16, HGNN_ERR_BAD_SHAPE, "unknown dtype %d", dtype);
+  return HGNN_OK;
+}
+
+}  // namespace hgnn
+
+using namespace hgnn;
+
+extern "C" int32_t hgnn_embed_fwd(void* stream, int32_t N, int32_t H, const int32_t* Z, const float* emb, float* h) {
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  HGNN_REQUIRE(N >= 0 && valid_H(H), HGNN_ERR_BAD_SHAPE, "embed_fwd: bad N or H");
+  if (N == 0) return HGNN_OK;
+  HGNN_REQUIRE(Z && emb && h, HGNN_ERR_NULLPTR, "embed_fwd: null pointer");
+  k_embed_fwd<<<nb64((int64_t)N * (H / 4), 256), 256, 0, st>>>(N, H, Z, emb, h);
+  HGNN_LAUNCH_CHECK("k_embed_fwd");
+  return HGNN_OK;
+}
+
+extern "C" int32_t hgnn_embed_bwd(void* stream, int32_t N, int32_t H, const int32_t* Z, const float* g_h, float* g_emb) {
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  HGNN_REQUIRE(N >= 0 && valid_H(H), HGNN_ERR_BAD_SHAPE, "embed_bwd: bad N or H");
+  HGNN_REQUIRE(g_emb && (N == 0 || (Z && g_h)), HGNN_ERR_NULLPTR, "embed_bwd: null pointer");
+  k_embed_bwd<<<HGNN_ZMAX + 1, 256, 0, st>>>(N, H, Z, g_h, g_emb);
+  HGNN_LAUNCH_CHECK("k_embed_bwd");
+  return HGNN_OK;
+}
+
+extern "C" int32_t hgnn_pool_by_graph_fwd(void* stream, int32_t N, int32_t G, int32_t H, int32_t mode,
+                                          const int32_t* graph_off, const float* h, float* p) {
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  HGNN_REQUIRE(N >= 0 && G >= 0 && valid_H(H), HGNN_ERR_BAD_SHAPE, "pool_fwd: bad N, G or H");
+  HGNN_REQUIRE(mode == HGNN_POOL_SUM || mode == HGNN_POOL_MEAN, HGNN_ERR_BAD_SHAPE, "pool_fwd: unknown mode");
+  if (G == 0) return HGNN_OK;
+  HGNN_REQUIRE(graph_off && p && (h || N == 0), HGNN_ERR_NULLPTR, "pool_fwd: null pointer");
+  k_pool_fwd<<<G, 1024, 0, st>>>(H, mode, graph_off, h, p);
+  HGNN_LAUNCH_CHECK("k_pool_fwd");
+  return HGNN_OK;
+}
+
+extern "C" int32_t hgnn_pool_by_graph_bwd(void* stream, int32_t N, int32_t G, int32_t H, int32_t mode,
+                                          const int32_t* graph_off, const float* g_p, float* g_h, int32_t accumulate) {
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  HGNN_REQUIRE(N >= 0 && G >= 0 && valid_H(H), HGNN_ERR_BAD_SHAPE, "pool_bwd: bad N, G or H");
+  HGNN_REQUIRE(mode == HGNN_POOL_SUM || mode == HGNN_POOL_MEAN, HGNN_ERR_BAD_SHAPE, "pool_bwd: unknown mode");
+  if (N == 0) return HGNN_OK;
+  HGNN_REQUIRE(G > 0 && graph_off && g_p && g_h, HGNN_ERR_NULLPTR, "pool_bwd: null pointer");
+  k_pool_bwd<<<nb64((int64_t)N * (H / 4), 256), 256, 0, st>>>(N, G, H, mode, graph_off, g_p, g_h, accumulate);
+  HGNN_LAUNCH_CHECK("k_pool_bwd");
+  return HGNN_OK;
+}
+
+extern "C" int64_t hgnn_multihead_plan_ints(int32_t N, int32_t G, int32_t S) {
+  if (N < 0 || G < 0 || S < 1) return -1;
+  return plan_view<int32_t>(nullptr, N, G, S).ints;
+}
+
+extern "C" int32_t hgnn_multihead_plan(void* stream, int32_t N, int32_t G, int32_t S, const int32_t* graph_off,
+                                       const int32_t* source_id, int32_t* plan) {
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  HGNN_REQUIRE(N >= 0 && G >= 0, HGNN_ERR_BAD_SHAPE, "negative N or G");
+  HGNN_REQUIRE(S >= 1 && S <= 65535, HGNN_ERR_BAD_SHAPE, "S must be in 1..65535 (got %d)", S);
+  HGNN_REQUIRE(plan && graph_off && (source_id || G == 0), HGNN_ERR_NULLPTR, "multihead_plan: null pointer");
+  PlanView v = plan_view(plan, N, G, S);
+  k_plan_graphs<<<1, 1024, 0, st>>>(G, S, graph_off, source_id, v);
+  HGNN_LAUNCH_CHECK("k_plan_graphs");
+  int32_t status = 0;
+  HGNN_HIP(hipMemcpyAsync(&status, v.status, sizeof(status), hipMemcpyDeviceToHost, st));
+  HGNN_HIP(hipStreamSynchronize(st));
+  HGNN_REQUIRE(status == 0, HGNN_ERR_BAD_SOURCE_ID, "a source id lies outside [0, %d)", S);
+  if (N > 0) {
+    k_plan_atoms<<<nb64(N, 256), 256, 0, st>>>(N, G, graph_off, v);
+    HGNN_LAUNCH_CHECK("k_plan_atoms");
+  }
+  return HGNN_OK;
+}
+
+extern "C" int32_t hgnn_multihead_decode_workspace_bytes(int32_t N, int32_t G, int32_t H, int32_t Hh, int32_t S,
+                                                         int32_t dtype, size_t* ws_bytes_host,
+                                                         size_t* saved_bytes_host) {
+  HGNN_TRY(check_head_args(N, G, H, Hh, S, dtype));
+  HGNN_REQUIRE(ws_bytes_host && saved_bytes_host, HGNN_ERR_NULLPTR, "null size pointer");
+  *ws_bytes_host = carve_head_ws(nullptr, N, G, H, Hh, S, dtype == HGNN_BF16).bytes;
+  *saved_bytes_host = carve_head_saved(nullptr, N, G, Hh).bytes;
+  return HGNN_OK;
+}
+
+extern "C" int32_t hgnn_multihead_decode_fwd(void* stream, int32_t N, int32_t G, int32_t H, int32_t Hh, int32_t S,
+                                             int32_t dtype, const int32_t* plan, const float* p, const float* h,
+                                             const float* v, const float* Whead, float* energy, float* force,
+                                             void* saved, size_t saved_bytes, void* ws, size_t ws_bytes) {
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  HGNN_TRY(check_head_args(N, G, H, Hh, S, dtype));
+  if (G == 0 && N == 0) return HGNN_OK;
+  HGNN_REQUIRE(plan && Whead && saved && ws, HGNN_ERR_NULLPTR, "multihead_decode_fwd: null pointer");
+  HGNN_REQUIRE((G == 0 || (p && energy)) && (N == 0 || (h && v && force)), HGNN_ERR_NULLPTR,
+               "multihead_decode_fwd: null pointer");
+  const bool bf16 = dtype == HGNN_BF16;
+  HeadWs w = carve_head_ws(ws, N, G, H, Hh, S, bf16);
+  HeadSaved s = carve_head_saved(saved, N, G, Hh);
+  HGNN_REQUIRE(ws_bytes >= w.bytes, HGNN_ERR_WORKSPACE_TOO_SMALL, "decode workspace: need %zu bytes, got %zu", w.bytes, ws_bytes);
+  HGNN_REQUIRE(saved_bytes >= s.bytes, HGNN_ERR_WORKSPACE_TOO_SMALL, "decode saved buffer: need %zu bytes, got %zu", s.bytes, saved_bytes);
+  PlanView pv = plan_view(plan, N, G, S);
+  const HeadOff o(H, Hh);
+  const long HH = (long)H * H;
+
+  PackArgs pk;
+  pk.src = Whead;
+  pk.dst = w.packed;
+  pk.nblocks = 2;
+  pk.d[0] = {o.We1, Hh, 1};
+  pk.d[1] = {o.Wf1, Hh, 1};
+  HGNN_TRY(launch_pack(st, H, bf16, pk, S, o.per, 2 * HH));
+  if (G > 0) {
+    GemmArgs g;
+    g.A[0] = p; g.lda[0] = H;
+    g.B = w.packed; g.blk[0][0] = 0; g.grp_blk_stride = 2;
+    g.row_idx = pv.graph_perm; g.grp_ptr = pv.grp_graph_ptr; g.S = S; g.M = G;
+    g.bias = Whead + o.be1; g.bias_cb_mask = 1; g.grp_bias_stride = o.per;
+    g.C = s.ze; g.ldc = Hh;
+    HGNN_TRY(launch_gemm(st, H, bf16, g));
+  }
+  if (N > 0) {
+    GemmArgs g;
+    g.A[0] = h; g.lda[0] = H;
+    g.B = w.packed; g.blk[0][0] = 1; g.grp_blk_stride = 2;
+    g.row_idx = pv.atom_perm; g.grp_ptr = pv.grp_atom_ptr; g.S = S; g.M = N;
+    g.bias = Whead + o.bf1; g.bias_cb_mask = 1; g.grp_bias_stride = o.per;
+    g.C = s.zf; g.ldc = Hh;
+    HGNN_TRY(launch_gemm(st, H, bf16, g));
+  }
+  k_head_out_fwd<<<nb64((int64_t)(G + N) * 64, 256), 256, 0, st>>>(N, G, Hh, s.ze, s.zf, Whead, o, pv.graph_src,
+                                                                    pv.atom_graph, v, energy, force, s.q);
+  HGNN_LAUNCH_CHECK("k_head_out_fwd");
+  return HGNN_OK;
+}
+
+extern "C" int32_t hgnn_multihead_decode_bwd(void* stream, int32_t N, int32_t G, int32_t H, int32_t Hh, int32_t S,
+                                             int32_t dtype, const int32_t* plan, const float* p, const float* h,
+                                             const float* v, const float* Whead, const void* saved,
+                                             size_t saved_bytes, const float* g_energy, const float* g_force,
+                                             float* g_p, float* g_h, float* g_v, float* gWhead, void* ws,
+                                             size_t ws_bytes) {
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  HGNN_TRY(check_head_args(N, G, H, Hh, S, dtype));
+  HGNN_REQUIRE(gWhead && Whead && ws, HGNN_ERR_NULLPTR, "multihead_decode_bwd: null pointer");
+  const HeadOff o(H, Hh);
+  if (G == 0 && N == 0) return launch_fill_f32(st, gWhead, o.per * S, 0.f);
+  HGNN_REQUIRE(plan && saved, HGNN_ERR_NULLPTR, "multihead_decode_bwd: null pointer");
+  HGNN_REQUIRE((G == 0 || (p && g_energy && g_p)) && (N == 0 || (h && v && g_force && g_h && g_v)), HGNN_ERR_NULLPTR,
+               "multihead_decode_bwd: null pointer");
+  const bool bf16 = dtype == HGNN_BF16;
+  HeadWs w = carve_head_ws(ws, N, G, H, Hh, S, bf16);
+  HeadSaved s = carve_head_saved(const_cast<void*>(saved), N, G, Hh);
+  HGNN_REQUIRE(ws_bytes >= w.bytes, HGNN_ERR_WORKSPACE_TOO_SMALL, "decode workspace: need %zu bytes, got %zu", w.bytes, ws_bytes);
+  HGNN_REQUIRE(saved_bytes >= s.bytes, HGNN_ERR_WORKSPACE_TOO_SMALL, "decode saved buffer: need %zu bytes, got %zu", s.bytes, saved_bytes);
+  PlanView pv = plan_view(plan, N, G, S);
+  const long HH = (long)H * H;
+
+  PackArgs pk;  // transposed first layers
+  pk.src = Whead;
+  pk.dst = w.packed;
+  pk.nblocks = 2;
+  pk.d[0] = {o.We1, 1, Hh};
+  pk.d[1] = {o.Wf1, 1, Hh};
+  HGNN_TRY(launch_pack(st, H, bf16, pk, S, o.per, 2 * HH));
+
+  k_head_out_bwd<<<nb64((int64_t)(G + N) * 64, 256), 256, 0, st>>>(N, G, Hh, s.ze, s.zf, Whead, o, pv.graph_src,
+                                                                    pv.atom_graph, v, s.q, g_energy, g_force, w.g_ze,
+                                                                    w.g_zf, w.gq, g_v);
+  HGNN_LAUNCH_CHECK("k_head_out_bwd");
+
+  // ---- energy branch (rows = graphs) and force branch (rows = atoms), same five steps each
+  for (int br = 0; br < 2; ++br) {
+    const bool en = br == 0;
+    const int64_t M = en ? G : N;
+    const int32_t* ridx = en ? pv.graph_perm : pv.atom_perm;
+    const int32_t* gptr = en ? pv.grp_graph_ptr : pv.grp_atom_ptr;
+    const float* X = en ? p : h;              // first-layer input
+    const float* z = en ? s.ze : s.zf;
+    float* gz = en ? w.g_ze : w.g_zf;
+    const float* gout = en ? g_energy : w.gq;  // per-row upstream scalar
+    const long oW1 = en ? o.We1 : o.Wf1, ob1 = en ? o.be1 : o.bf1, oW2 = en ? o.We2 : o.Wf2, ob2 = en ? o.be2 : o.bf2;
+    if (M == 0) {
+      // nothing routed anywhere: this branch's gradients are zero for every source
+      for (int sidx = 0; sidx < S; ++sidx)
+        HGNN_TRY(launch_fill_f32(st, gWhead + sidx * o.per + oW1, (int64_t)H * Hh + 2 * Hh + 1, 0.f));
+      continue;
+    }
+    {  // second layer weight and bias
+      ColsumArgs c;
+      c.X = z; c.ldx = Hh; c.f_silu = 1; c.w = gout; c.row_idx = ridx; c.grp_ptr = gptr; c.S = S; c.M = M;
+      c.dest = gWhead + oW2; c.grp_dest_stride = o.per; c.partial = w.partial;
+      HGNN_TRY(launch_colsum(st, Hh, c));
+      k_group_scalar_sum<<<S, 64, 0, st>>>(gout, ridx, gptr, gWhead + ob2, o.per);
+      HGNN_LAUNCH_CHECK("k_group_scalar_sum");
+    }
+    {  // first layer bias and weight
+      ColsumArgs c;
+      c.X = gz; c.ldx = Hh; c.row_idx = ridx; c.grp_ptr = gptr; c.S = S; c.M = M;
+      c.dest = gWhead + ob1; c.grp_dest_stride = o.per; c.partial = w.partial;
+      HGNN_TRY(launch_colsum(st, Hh, c));
+      WgradArgs a;
+      a.A[0] = X; a.lda[0] = H;
+      a.B[0] = gz; a.ldb[0] = Hh;
+      a.row_idx = ridx; a.grp_ptr = gptr; a.S = S; a.M = M;
+      a.dest[0] = gWhead + oW1; a.grp_dest_stride = o.per;
+      a.partial = w.partial;
+      HGNN_TRY(launch_wgrad(st, H, bf16, a));
+    }
+    {  // input gradient
+      GemmArgs g;
+      g.A[0] = gz; g.lda[0] = Hh;
+      g.B = w.packed; g.blk[0][0] = en ? 0 : 1; g.grp_blk_stride = 2;
+      g.row_idx = ridx; g.grp_ptr = gptr; g.S = S; g.M = (int)M;
+      g.C = en ? g_p : g_h; g.ldc = H;
+      HGNN_TRY(launch_gemm(st, H, bf16, g));
+    }
+  }
+  return HGNN_OK;
+}

@@ -1,0 +1,644 @@
+// Radius graph on the GPU: cell-list candidate search, exact float32 cutoff test, destination-sorted
+// CSR with rows ordered by (source, shift), and the source-sorted transpose plan.
+//
+// Design for gfx950: one wavefront per destination atom walks the (2R+1)^3 block of bins around the
+// atom's own bin (bins live in fractional coordinates of the graph's cell, at least one cutoff wide
+// wherever the cell allows it; cells thinner than the cutoff are covered by integer image shifts
+// instead), lanes take candidate atoms, hits are compacted with a ballot. Row order is restored
+// afterwards by ranking each hit against the other hits of its row, which needs no global sort.
+// Only integer atomics are used (bin histogram / cursors); the output does not depend on their order.
+//
+// The cutoff test is the one fixed in include/hgnn.h: each float operation is an explicitly rounded
+// intrinsic so that the compiler cannot contract them into fused multiply-adds.
+#include "common.h"
+
+namespace hgnn {
+
+// ---------------------------------------------------------------------------------------------
+// error text (thread local), shared by all translation units
+// ---------------------------------------------------------------------------------------------
+static thread_local char g_err[512] = "";
+
+int32_t set_error(int32_t code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+// ---------------------------------------------------------------------------------------------
+// exclusive scan (three small kernels; block sums kept in int64 so that overflow is detectable)
+// ---------------------------------------------------------------------------------------------
+constexpr int SCAN_T = 256;
+constexpr int SCAN_PER = 4;
+constexpr int SCAN_BLK = SCAN_T * SCAN_PER;
+
+__device__ inline int block_exclusive_scan_256(int v, int* total, int* sh) {
+  // sh: 256 ints. Hillis-Steele inclusive scan, then shift.
+  const int t = threadIdx.x;
+  sh[t] = v;
+  __syncthreads();
+  for (int o = 1; o < SCAN_T; o <<= 1) {
+    int add = (t >= o) ? sh[t - o] : 0;
+    __syncthreads();
+    sh[t] += add;
+    __syncthreads();
+  }
+  int incl = sh[t];
+  *total = sh[SCAN_T - 1];
+  __syncthreads();
+  return incl - v;
+}
+
+__global__ void k_scan_local(const int32_t* __restrict__ in, int32_t* __restrict__ out, int64_t n,
+                             long long* __restrict__ blocksum) {
+  __shared__ int sh[SCAN_T];
+  const int64_t base = (int64_t)blockIdx.x * SCAN_BLK + (int64_t)threadIdx.x * SCAN_PER;
+  int v[SCAN_PER];
+  int s = 0;
+#pragma unroll
+  for (int k = 0; k < SCAN_PER; ++k) {
+    v[k] = (base + k < n) ? in[base + k] : 0;
+    s += v[k];
+  }
+  int tot;
+  int ex = block_exclusive_scan_256(s, &tot, sh);
+#pragma unroll
+  for (int k = 0; k < SCAN_PER; ++k) {
+    if (base + k < n) out[base + k] = ex;
+    ex += v[k];
+  }
+  if (threadIdx.x == 0) blocksum[blockIdx.x] = tot;
+}
+
+__global__ void k_scan_blocksums(long long* __restrict__ blocksum, int64_t nb) {
+  // single thread block; serial carry over chunks of 256 block sums (nb is small)
+  __shared__ long long sh[SCAN_T];
+  __shared__ long long carry;
+  if (threadIdx.x == 0) carry = 0;
+  __syncthreads();
+  for (int64_t c0 = 0; c0 < nb; c0 += SCAN_T) {
+    const int64_t idx = c0 + threadIdx.x;
+    long long v = idx < nb ? blocksum[idx] : 0;
+    sh[threadIdx.x] = v;
+    __syncthreads();
+    for (int o = 1; o < SCAN_T; o <<= 1) {
+      long long add = (threadIdx.x >= o) ? sh[threadIdx.x - o] : 0;
+      __syncthreads();
+      sh[threadIdx.x] += add;
+      __syncthreads();
+    }
+    long long incl = sh[threadIdx.x];
+    long long c = carry;
+    if (idx < nb) blocksum[idx] = c + incl - v;
+    __syncthreads();
+    if (threadIdx.x == SCAN_T - 1) carry = c + incl;
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) blocksum[nb] = carry;  // grand total
+}
+
+__global__ void k_scan_add(int32_t* __restrict__ out, int64_t n, const long long* __restrict__ blocksum,
+                           int64_t nb) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) out[i] = (int32_t)(out[i] + blocksum[i / SCAN_BLK]);
+  if (i == n) out[n] = (int32_t)blocksum[nb];
+}
+
+size_t scan_scratch_ints(int64_t n) {
+  int64_t nb = (n + SCAN_BLK - 1) / SCAN_BLK;
+  return (size_t)(2 * (nb + 2));  // int64 entries counted in int32 units
+}
+
+int32_t exclusive_scan_i32(hipStream_t st, const int32_t* in, int32_t* out, int64_t n, int32_t* scratch) {
+  long long* bs = reinterpret_cast<long long*>(scratch);
+  int64_t nb = (n + SCAN_BLK - 1) / SCAN_BLK;
+  if (nb > 0) {
+    k_scan_local<<<dim3((unsigned)nb), dim3(SCAN_T), 0, st>>>(in, out, n, bs);
+    HGNN_LAUNCH_CHECK("k_scan_local");
+  }
+  k_scan_blocksums<<<dim3(1), dim3(SCAN_T), 0, st>>>(bs, nb);
+  HGNN_LAUNCH_CHECK("k_scan_blocksums");
+  int64_t tot = n + 1;
+  k_scan_add<<<dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, st>>>(out, n, bs, nb);
+  HGNN_LAUNCH_CHECK("k_scan_add");
+  return HGNN_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// per-graph metadata
+// ---------------------------------------------------------------------------------------------
+struct GMeta {
+  float cell[9];   // rows a, b, c (zeros when not periodic)
+  float inv[9];    // fractional = (pos - org) * inv   (row vector times matrix)
+  float org[3];
+  int nb[3];       // bins per lattice direction
+  int R[3];        // search reach in bins
+  int bin_off;     // first global bin of this graph (filled after the scan)
+  int periodic;
+  int lo, hi;      // atom range
+};
+
+enum : int {
+  ST_BAD_OFFSETS = 1,
+  ST_BAD_CELL = 2,
+};
+
+constexpr float BIN_MARGIN = 1.001f;  // bins are at least 1.001 * rc wide: absorbs float32 binning error
+constexpr int NB_MAX = 256;
+
+__global__ void k_fill_i32(int32_t* p, int64_t n, int32_t v) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+
+__device__ inline float wave_min(float x) {
+  for (int o = 32; o > 0; o >>= 1) x = fminf(x, __shfl_xor(x, o));
+  return x;
+}
+__device__ inline float wave_max(float x) {
+  for (int o = 32; o > 0; o >>= 1) x = fmaxf(x, __shfl_xor(x, o));
+  return x;
+}
+
+// one wavefront (block of 64) per graph
+__global__ void k_graph_meta(int N, int G, const float* __restrict__ pos, const int32_t* __restrict__ graph_off,
+                             const float* __restrict__ cell, const uint8_t* __restrict__ pbc, float rc,
+                             GMeta* __restrict__ meta, int32_t* __restrict__ nbins, int32_t* __restrict__ status) {
+  const int g = blockIdx.x;
+  const int lane = threadIdx.x;
+  int lo = graph_off[g], hi = graph_off[g + 1];
+  bool bad = (lo > hi) || (lo < 0) || (hi > N) || (g == 0 && lo != 0) || (g == G - 1 && hi != N);
+  if (bad) {
+    if (lane == 0) {
+      atomicOr(status, ST_BAD_OFFSETS);
+      GMeta m = {};
+      m.nb[0] = m.nb[1] = m.nb[2] = 1;
+      meta[g] = m;
+      nbins[g] = 1;
+    }
+    return;
+  }
+  const bool periodic = (pbc != nullptr) && (cell != nullptr) && (pbc[g] != 0);
+  float mn[3] = {3.0e38f, 3.0e38f, 3.0e38f}, mx[3] = {-3.0e38f, -3.0e38f, -3.0e38f};
+  if (!periodic) {
+    for (int i = lo + lane; i < hi; i += 64) {
+#pragma unroll
+      for (int c = 0; c < 3; ++c) {
+        float x = pos[3 * (size_t)i + c];
+        mn[c] = fminf(mn[c], x);
+        mx[c] = fmaxf(mx[c], x);
+      }
+    }
+#pragma unroll
+    for (int c = 0; c < 3; ++c) {
+      mn[c] = wave_min(mn[c]);
+      mx[c] = wave_max(mx[c]);
+    }
+  }
+  if (lane != 0) return;
+  GMeta m = {};
+  m.lo = lo;
+  m.hi = hi;
+  m.periodic = periodic ? 1 : 0;
+  const double rcm = (double)rc * (double)BIN_MARGIN;
+  double hgt[3];
+  if (periodic) {
+    double C[9];
+    for (int k = 0; k < 9; ++k) {
+      m.cell[k] = cell[9 * (size_t)g + k];
+      C[k] = (double)m.cell[k];
+    }
+    // cross products of the other two lattice vectors
+    double cr[3][3];
+    for (int k = 0; k < 3; ++k) {
+      const double* u = &C[3 * ((k + 1) % 3)];
+      const double* w = &C[3 * ((k + 2) % 3)];
+      cr[k][0] = u[1] * w[2] - u[2] * w[1];
+      cr[k][1] = u[2] * w[0] - u[0] * w[2];
+      cr[k][2] = u[0] * w[1] - u[1] * w[0];
+    }
+    double det = C[0] * cr[0][0] + C[1] * cr[0][1] + C[2] * cr[0][2];
+    if (!(fabs(det) >= 1e-6)) {
+      atomicOr(status, ST_BAD_CELL);
+      m.nb[0] = m.nb[1] = m.nb[2] = 1;
+      m.periodic = 0;
+      meta[g] = m;
+      nbins[g] = 1;
+      return;
+    }
+    // inverse: column k of C^-1 is cr[k] / det  (f_k = (pos . cr[k]) / det)
+    for (int k = 0; k < 3; ++k) {
+      double nrm = sqrt(cr[k][0] * cr[k][0] + cr[k][1] * cr[k][1] + cr[k][2] * cr[k][2]);
+      hgt[k] = fabs(det) / nrm;
+      for (int c = 0; c < 3; ++c) m.inv[3 * c + k] = (float)(cr[k][c] / det);
+    }
+    m.org[0] = m.org[1] = m.org[2] = 0.f;
+  } else {
+    for (int c = 0; c < 3; ++c) {
+      if (hi == lo) { mn[c] = 0.f; mx[c] = 0.f; }
+      double ext = (double)mx[c] - (double)mn[c];
+      double pad = 1e-3 * (1.0 + ext);
+      hgt[c] = ext + 2.0 * pad;
+      m.org[c] = (float)((double)mn[c] - pad);
+      m.inv[3 * c + c] = (float)(1.0 / hgt[c]);
+    }
+  }
+  long long nat = hi - lo;
+  int nb[3];
+  for (int k = 0; k < 3; ++k) {
+    double q = floor(hgt[k] / rcm);
+    nb[k] = q < 1.0 ? 1 : (q > (double)NB_MAX ? NB_MAX : (int)q);
+  }
+  // keep the number of bins proportional to the number of atoms (bounded workspace)
+  long long cap = 4 * nat > 1 ? 4 * nat : 1;
+  while ((long long)nb[0] * nb[1] * nb[2] > cap) {
+    int k = (nb[0] >= nb[1] && nb[0] >= nb[2]) ? 0 : (nb[1] >= nb[2] ? 1 : 2);
+    nb[k] -= 1;
+  }
+  for (int k = 0; k < 3; ++k) {
+    double w = hgt[k] / nb[k];
+    int R = (int)ceil(rcm / w);
+    if (R < 1) R = 1;
+    if (!periodic && R > nb[k] - 1) R = nb[k] - 1;  // nothing outside the bounding box
+    if (R > 127) {
+      atomicOr(status, ST_BAD_CELL);
+      R = 0;
+    }
+    m.nb[k] = nb[k];
+    m.R[k] = R;
+  }
+  meta[g] = m;
+  nbins[g] = nb[0] * nb[1] * nb[2];
+}
+
+__global__ void k_set_bin_off(int G, GMeta* __restrict__ meta, const int32_t* __restrict__ bin_off) {
+  int g = blockIdx.x * blockDim.x + threadIdx.x;
+  if (g < G) meta[g].bin_off = bin_off[g];
+}
+
+__device__ inline int find_graph(const int32_t* __restrict__ graph_off, int G, int i) {
+  // largest g with graph_off[g] <= i  (empty graphs share an offset; the last of them wins, and its
+  // successor is the one that really holds atom i) -> search for the first g with graph_off[g+1] > i
+  int lo = 0, hi = G - 1;
+  while (lo < hi) {
+    int mid = (lo + hi) >> 1;
+    if (graph_off[mid + 1] > i) hi = mid; else lo = mid + 1;
+  }
+  return lo;
+}
+
+__global__ void k_bin_atoms_count(int N, int G, const float* __restrict__ pos, const int32_t* __restrict__ graph_off,
+                                  const GMeta* __restrict__ meta, int32_t* __restrict__ atom_graph,
+                                  int32_t* __restrict__ atom_bin, int32_t* __restrict__ bin_cnt) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= N) return;
+  int g = find_graph(graph_off, G, i);
+  const GMeta& m = meta[g];
+  float d[3] = {pos[3 * (size_t)i] - m.org[0], pos[3 * (size_t)i + 1] - m.org[1], pos[3 * (size_t)i + 2] - m.org[2]};
+  int b[3];
+#pragma unroll
+  for (int k = 0; k < 3; ++k) {
+    float f = d[0] * m.inv[k] + d[1] * m.inv[3 + k] + d[2] * m.inv[6 + k];
+    int q = (int)floorf(f * (float)m.nb[k]);
+    b[k] = q < 0 ? 0 : (q >= m.nb[k] ? m.nb[k] - 1 : q);
+  }
+  int bin = m.bin_off + (b[0] * m.nb[1] + b[1]) * m.nb[2] + b[2];
+  atom_graph[i] = g;
+  atom_bin[i] = bin;
+  atomicAdd(&bin_cnt[bin], 1);
+}
+
+__global__ void k_bin_atoms_fill(int N, const int32_t* __restrict__ atom_bin, const int32_t* __restrict__ bin_start,
+                                 int32_t* __restrict__ bin_cur, int32_t* __restrict__ bin_atoms) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= N) return;
+  int bin = atom_bin[i];
+  int k = atomicAdd(&bin_cur[bin], 1);
+  bin_atoms[bin_start[bin] + k] = i;
+}
+
+// ---------------------------------------------------------------------------------------------
+// candidate walk: one wavefront per destination atom
+// ---------------------------------------------------------------------------------------------
+__device__ inline int floordiv(int a, int b) { return (a >= 0) ? a / b : -((-a + b - 1) / b); }
+
+template <bool FILL>
+__global__ void __launch_bounds__(256)
+k_neighbors(int N, const float* __restrict__ pos, const GMeta* __restrict__ meta,
+            const int32_t* __restrict__ atom_graph, const int32_t* __restrict__ atom_bin,
+            const int32_t* __restrict__ bin_start, const int32_t* __restrict__ bin_atoms, float rc,
+            int32_t* __restrict__ deg, const int32_t* __restrict__ row_ptr,
+            int32_t* __restrict__ key_j, int32_t* __restrict__ key_c) {
+  const int i = (int)(((size_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6);
+  const int lane = threadIdx.x & 63;
+  if (i >= N) return;
+  const GMeta& m = meta[atom_graph[i]];
+  const int nb0 = m.nb[0], nb1 = m.nb[1], nb2 = m.nb[2];
+  const int lb = atom_bin[i] - m.bin_off;
+  const int b2 = lb % nb2, b1 = (lb / nb2) % nb1, b0 = lb / (nb1 * nb2);
+  const float pix = pos[3 * (size_t)i], piy = pos[3 * (size_t)i + 1], piz = pos[3 * (size_t)i + 2];
+  const float rc2 = __fmul_rn(rc, rc);
+  const bool per = m.periodic != 0;
+  int count = 0;
+  const int base = FILL ? row_ptr[i] : 0;
+  for (int B0 = b0 - m.R[0]; B0 <= b0 + m.R[0]; ++B0) {
+    int s0 = 0, c0 = B0;
+    if (per) { s0 = floordiv(B0, nb0); c0 = B0 - s0 * nb0; } else if (B0 < 0 || B0 >= nb0) continue;
+    for (int B1 = b1 - m.R[1]; B1 <= b1 + m.R[1]; ++B1) {
+      int s1 = 0, c1 = B1;
+      if (per) { s1 = floordiv(B1, nb1); c1 = B1 - s1 * nb1; } else if (B1 < 0 || B1 >= nb1) continue;
+      for (int B2 = b2 - m.R[2]; B2 <= b2 + m.R[2]; ++B2) {
+        int s2 = 0, c2 = B2;
+        if (per) { s2 = floordiv(B2, nb2); c2 = B2 - s2 * nb2; } else if (B2 < 0 || B2 >= nb2) continue;
+        const int bin = m.bin_off + (c0 * nb1 + c1) * nb2 + c2;
+        const float f0 = (float)s0, f1 = (float)s1, f2 = (float)s2;
+        // t = (s0*a + s1*b) + s2*c, every operation rounded on its own
+        const float tx = __fadd_rn(__fadd_rn(__fmul_rn(f0, m.cell[0]), __fmul_rn(f1, m.cell[3])), __fmul_rn(f2, m.cell[6]));
+        const float ty = __fadd_rn(__fadd_rn(__fmul_rn(f0, m.cell[1]), __fmul_rn(f1, m.cell[4])), __fmul_rn(f2, m.cell[7]));
+        const float tz = __fadd_rn(__fadd_rn(__fmul_rn(f0, m.cell[2]), __fmul_rn(f1, m.cell[5])), __fmul_rn(f2, m.cell[8]));
+        const bool zero_shift = (s0 | s1 | s2) == 0;
+        const int code = ((s0 + 128) << 16) | ((s1 + 128) << 8) | (s2 + 128);
+        const int kb = bin_start[bin], ke = bin_start[bin + 1];
+        for (int k0 = kb; k0 < ke; k0 += 64) {
+          const int k = k0 + lane;
+          bool hit = false;
+          int j = 0;
+          if (k < ke) {
+            j = bin_atoms[k];
+            const float qx = __fadd_rn(pos[3 * (size_t)j], tx);
+            const float qy = __fadd_rn(pos[3 * (size_t)j + 1], ty);
+            const float qz = __fadd_rn(pos[3 * (size_t)j + 2], tz);
+            const float rx = __fsub_rn(pix, qx), ry = __fsub_rn(piy, qy), rz = __fsub_rn(piz, qz);
+            const float dd = __fadd_rn(__fadd_rn(__fmul_rn(rx, rx), __fmul_rn(ry, ry)), __fmul_rn(rz, rz));
+            hit = (dd < rc2) && !(zero_shift && j == i);
+          }
+          const unsigned long long mask = __ballot(hit);
+          if (FILL && hit) {
+            const int off = __popcll(mask & ((1ull << lane) - 1ull));
+            key_j[base + count + off] = j;
+            key_c[base + count + off] = code;
+          }
+          count += __popcll(mask);
+        }
+      }
+    }
+  }
+  if (!FILL && lane == 0) deg[i] = count;
+}
+
+// one wavefront per row: rank every hit among the hits of its row and emit the edge in that place
+__global__ void __launch_bounds__(256)
+k_emit_rows(int N, const float* __restrict__ pos, const GMeta* __restrict__ meta,
+            const int32_t* __restrict__ atom_graph, const int32_t* __restrict__ row_ptr,
+            const int32_t* __restrict__ key_j, const int32_t* __restrict__ key_c,
+            int32_t* __restrict__ dst, int32_t* __restrict__ col, int8_t* __restrict__ shift,
+            float* __restrict__ d2, float* __restrict__ rvec) {
+  const int i = (int)(((size_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6);
+  const int lane = threadIdx.x & 63;
+  if (i >= N) return;
+  const int start = row_ptr[i], end = row_ptr[i + 1];
+  if (start == end) return;
+  const GMeta& m = meta[atom_graph[i]];
+  const float pix = pos[3 * (size_t)i], piy = pos[3 * (size_t)i + 1], piz = pos[3 * (size_t)i + 2];
+  for (int t = start + lane; t < end; t += 64) {
+    const int mj = key_j[t], mc = key_c[t];
+    int rank = 0;
+    for (int u = start; u < end; ++u) {
+      const int uj = key_j[u], uc = key_c[u];
+      rank += (uj < mj) || (uj == mj && uc < mc);
+    }
+    const int e = start + rank;
+    const int s0 = ((mc >> 16) & 255) - 128, s1 = ((mc >> 8) & 255) - 128, s2 = (mc & 255) - 128;
+    const float f0 = (float)s0, f1 = (float)s1, f2 = (float)s2;
+    const float tx = __fadd_rn(__fadd_rn(__fmul_rn(f0, m.cell[0]), __fmul_rn(f1, m.cell[3])), __fmul_rn(f2, m.cell[6]));
+    const float ty = __fadd_rn(__fadd_rn(__fmul_rn(f0, m.cell[1]), __fmul_rn(f1, m.cell[4])), __fmul_rn(f2, m.cell[7]));
+    const float tz = __fadd_rn(__fadd_rn(__fmul_rn(f0, m.cell[2]), __fmul_rn(f1, m.cell[5])), __fmul_rn(f2, m.cell[8]));
+    const float qx = __fadd_rn(pos[3 * (size_t)mj], tx);
+    const float qy = __fadd_rn(pos[3 * (size_t)mj + 1], ty);
+    const float qz = __fadd_rn(pos[3 * (size_t)mj + 2], tz);
+    const float rx = __fsub_rn(pix, qx), ry = __fsub_rn(piy, qy), rz = __fsub_rn(piz, qz);
+    const float dd = __fadd_rn(__fadd_rn(__fmul_rn(rx, rx), __fmul_rn(ry, ry)), __fmul_rn(rz, rz));
+    dst[e] = i;
+    col[e] = mj;
+    shift[3 * (size_t)e] = (int8_t)s0;
+    shift[3 * (size_t)e + 1] = (int8_t)s1;
+    shift[3 * (size_t)e + 2] = (int8_t)s2;
+    d2[e] = dd;
+    rvec[3 * (size_t)e] = rx;
+    rvec[3 * (size_t)e + 1] = ry;
+    rvec[3 * (size_t)e + 2] = rz;
+  }
+}
+
+__global__ void k_edge_graph_ptr(int G, const int32_t* __restrict__ graph_off, const int32_t* __restrict__ row_ptr,
+                                 int32_t* __restrict__ egp) {
+  int g = blockIdx.x * blockDim.x + threadIdx.x;
+  if (g <= G) egp[g] = row_ptr[graph_off[g]];
+}
+
+// ---------------------------------------------------------------------------------------------
+// transpose plan
+// ---------------------------------------------------------------------------------------------
+__global__ void k_count_sources(int64_t E, const int32_t* __restrict__ col, int32_t* __restrict__ cnt) {
+  int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (e < E) atomicAdd(&cnt[col[e]], 1);
+}
+
+__global__ void k_fill_sources(int64_t E, const int32_t* __restrict__ col, const int32_t* __restrict__ colT_ptr,
+                               int32_t* __restrict__ cur, int32_t* __restrict__ unsorted) {
+  int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= E) return;
+  int j = col[e];
+  int k = atomicAdd(&cur[j], 1);
+  unsorted[colT_ptr[j] + k] = (int32_t)e;
+}
+
+__global__ void __launch_bounds__(256)
+k_rank_sources(int N, const int32_t* __restrict__ colT_ptr, const int32_t* __restrict__ unsorted,
+               int32_t* __restrict__ permT) {
+  const int j = (int)(((size_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6);
+  const int lane = threadIdx.x & 63;
+  if (j >= N) return;
+  const int start = colT_ptr[j], end = colT_ptr[j + 1];
+  for (int t = start + lane; t < end; t += 64) {
+    const int me = unsorted[t];
+    int rank = 0;
+    for (int u = start; u < end; ++u) rank += unsorted[u] < me;
+    permT[start + rank] = me;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// workspace layout
+// ---------------------------------------------------------------------------------------------
+struct NeighWs {
+  int32_t* status;      // [4]
+  GMeta* meta;          // [G]
+  int32_t* nbins;       // [G]
+  int32_t* bin_off;     // [G+1]
+  int32_t* atom_graph;  // [N]
+  int32_t* atom_bin;    // [N]
+  int32_t* bin_cnt;     // [maxbins]
+  int32_t* bin_start;   // [maxbins+1]
+  int32_t* bin_cur;     // [maxbins]
+  int32_t* bin_atoms;   // [N]
+  int32_t* deg;         // [N]
+  int32_t* colT_cnt;    // [N]
+  int32_t* colT_cur;    // [N]
+  int32_t* scan;        // scratch
+  size_t bytes;
+  int64_t maxbins;
+};
+
+static NeighWs carve_neigh(void* ws, int N, int G) {
+  NeighWs w;
+  Carver c(ws);
+  w.maxbins = 4ll * N + G + 1;
+  w.status = c.take<int32_t>(4);
+  w.meta = c.take<GMeta>((size_t)G + 1);
+  w.nbins = c.take<int32_t>((size_t)G + 1);
+  w.bin_off = c.take<int32_t>((size_t)G + 2);
+  w.atom_graph = c.take<int32_t>((size_t)N + 1);
+  w.atom_bin = c.take<int32_t>((size_t)N + 1);
+  w.bin_cnt = c.take<int32_t>((size_t)w.maxbins);
+  w.bin_start = c.take<int32_t>((size_t)w.maxbins + 1);
+  w.bin_cur = c.take<int32_t>((size_t)w.maxbins);
+  w.bin_atoms = c.take<int32_t>((size_t)N + 1);
+  w.deg = c.take<int32_t>((size_t)N + 1);
+  w.colT_cnt = c.take<int32_t>((size_t)N + 1);
+  w.colT_cur = c.take<int32_t>((size_t)N + 1);
+  w.scan = c.take<int32_t>(scan_scratch_ints(w.maxbins + N + G + 8) + 8);
+  w.bytes = c.used();
+  return w;
+}
+
+static inline unsigned nblk(int64_t n, int t) { return (unsigned)((n + t - 1) / t); }
+
+}  // namespace hgnn
+
+using namespace hgnn;
+
+extern "C" const char* hgnn_last_error_string(void) { return g_err; }
+extern "C" int32_t hgnn_version(void) { return 1; }
+
+extern "C" int32_t hgnn_radius_graph_workspace_bytes(int32_t N, int32_t G, size_t* bytes_host) {
+  HGNN_REQUIRE(bytes_host != nullptr, HGNN_ERR_NULLPTR, "bytes_host is null");
+  HGNN_REQUIRE(N >= 0 && G >= 0, HGNN_ERR_BAD_SHAPE, "negative N or G");
+  *bytes_host = carve_neigh(nullptr, N, G).bytes;
+  return HGNN_OK;
+}
+
+extern "C" int32_t hgnn_radius_graph_count(void* stream, int32_t N, int32_t G, const float* pos,
+                                           const int32_t* graph_off, const float* cell, const uint8_t* pbc,
+                                           float rc, void* ws, size_t ws_bytes, int32_t* row_ptr,
+                                           int64_t* E_host) {
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  HGNN_REQUIRE(N >= 0 && G >= 0, HGNN_ERR_BAD_SHAPE, "negative N or G");
+  HGNN_REQUIRE(E_host && row_ptr && graph_off && ws, HGNN_ERR_NULLPTR, "radius_graph_count: null pointer");
+  HGNN_REQUIRE(pos || N == 0, HGNN_ERR_NULLPTR, "pos is null");
+  HGNN_REQUIRE(rc > 0.f && rc < 1e18f, HGNN_ERR_BAD_SHAPE, "cutoff must be positive");
+  HGNN_REQUIRE(G > 0 || N == 0, HGNN_ERR_BAD_OFFSETS, "atoms without a graph");
+  NeighWs w = carve_neigh(ws, N, G);
+  HGNN_REQUIRE(ws_bytes >= w.bytes, HGNN_ERR_WORKSPACE_TOO_SMALL, "radius graph workspace: need %zu bytes, got %zu",
+               w.bytes, ws_bytes);
+  *E_host = 0;
+  k_fill_i32<<<1, 64, 0, st>>>(w.status, 4, 0);
+  HGNN_LAUNCH_CHECK("k_fill_i32");
+  if (N == 0 || G == 0) {
+    k_fill_i32<<<1, 64, 0, st>>>(row_ptr, 1, 0);
+    HGNN_LAUNCH_CHECK("k_fill_i32");
+    HGNN_HIP(hipStreamSynchronize(st));
+    return HGNN_OK;
+  }
+  k_graph_meta<<<G, 64, 0, st>>>(N, G, pos, graph_off, cell, pbc, rc, w.meta, w.nbins, w.status);
+  HGNN_LAUNCH_CHECK("k_graph_meta");
+  HGNN_TRY(exclusive_scan_i32(st, w.nbins, w.bin_off, G, w.scan));
+  k_set_bin_off<<<nblk(G, 256), 256, 0, st>>>(G, w.meta, w.bin_off);
+  HGNN_LAUNCH_CHECK("k_set_bin_off");
+  // offsets must be valid before atoms are binned through them
+  int32_t status_h[4] = {0, 0, 0, 0};
+  HGNN_HIP(hipMemcpyAsync(status_h, w.status, sizeof(status_h), hipMemcpyDeviceToHost, st));
+  HGNN_HIP(hipStreamSynchronize(st));
+  HGNN_REQUIRE(!(status_h[0] & ST_BAD_OFFSETS), HGNN_ERR_BAD_OFFSETS,
+               "graph_off must start at 0, be non-decreasing and end at N");
+  HGNN_REQUIRE(!(status_h[0] & ST_BAD_CELL), HGNN_ERR_BAD_CELL,
+               "a periodic graph has a singular cell or needs more than 127 images per direction");
+  k_fill_i32<<<nblk(w.maxbins, 256), 256, 0, st>>>(w.bin_cnt, w.maxbins, 0);
+  k_fill_i32<<<nblk(w.maxbins, 256), 256, 0, st>>>(w.bin_cur, w.maxbins, 0);
+  HGNN_LAUNCH_CHECK("k_fill_i32");
+  k_bin_atoms_count<<<nblk(N, 256), 256, 0, st>>>(N, G, pos, graph_off, w.meta, w.atom_graph, w.atom_bin, w.bin_cnt);
+  HGNN_LAUNCH_CHECK("k_bin_atoms_count");
+  HGNN_TRY(exclusive_scan_i32(st, w.bin_cnt, w.bin_start, w.maxbins, w.scan));
+  k_bin_atoms_fill<<<nblk(N, 256), 256, 0, st>>>(N, w.atom_bin, w.bin_start, w.bin_cur, w.bin_atoms);
+  HGNN_LAUNCH_CHECK("k_bin_atoms_fill");
+  k_neighbors<false><<<nblk((int64_t)N * 64, 256), 256, 0, st>>>(N, pos, w.meta, w.atom_graph, w.atom_bin, w.bin_start,
+                                                                 w.bin_atoms, rc, w.deg, nullptr, nullptr, nullptr);
+  HGNN_LAUNCH_CHECK("k_neighbors<count>");
+  HGNN_TRY(exclusive_scan_i32(st, w.deg, row_ptr, N, w.scan));
+  // grand total (int64) sits behind the block sums of the last scan
+  int64_t nbs = ((int64_t)N + SCAN_BLK - 1) / SCAN_BLK;
+  long long total = 0;
+  HGNN_HIP(hipMemcpyAsync(&total, reinterpret_cast<long long*>(w.scan) + nbs, sizeof(total), hipMemcpyDeviceToHost, st));
+  HGNN_HIP(hipStreamSynchronize(st));
+  HGNN_REQUIRE(total < (1ll << 31), HGNN_ERR_OVERFLOW, "edge count %lld does not fit int32", total);
+  *E_host = total;
+  return HGNN_OK;
+}
+
+extern "C" int32_t hgnn_radius_graph_fill(void* stream, int32_t N, int32_t G, const float* pos,
+                                          const int32_t* graph_off, const float* cell, const uint8_t* pbc, float rc,
+                                          void* ws, size_t ws_bytes, void* tmp, size_t tmp_bytes,
+                                          const int32_t* row_ptr, int64_t E, int32_t* dst, int32_t* col,
+                                          int8_t* shift, float* d2, float* rvec, int32_t* edge_graph_ptr,
+                                          int32_t* colT_ptr, int32_t* permT) {
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  (void)cell; (void)pbc;
+  HGNN_REQUIRE(N >= 0 && G >= 0 && E >= 0, HGNN_ERR_BAD_SHAPE, "negative size");
+  HGNN_REQUIRE(E < (1ll << 31), HGNN_ERR_OVERFLOW, "edge count does not fit int32");
+  HGNN_REQUIRE(ws && row_ptr && graph_off && edge_graph_ptr && colT_ptr, HGNN_ERR_NULLPTR, "radius_graph_fill: null pointer");
+  HGNN_REQUIRE(E == 0 || (tmp && dst && col && shift && d2 && rvec && permT && pos), HGNN_ERR_NULLPTR,
+               "radius_graph_fill: null edge array");
+  HGNN_REQUIRE(rc > 0.f, HGNN_ERR_BAD_SHAPE, "cutoff must be positive");
+  NeighWs w = carve_neigh(ws, N, G);
+  HGNN_REQUIRE(ws_bytes >= w.bytes, HGNN_ERR_WORKSPACE_TOO_SMALL, "radius graph workspace too small");
+  HGNN_REQUIRE(tmp_bytes >= (size_t)E * 8, HGNN_ERR_WORKSPACE_TOO_SMALL, "radius graph tmp: need %zu bytes", (size_t)E * 8);
+  if (G > 0 || N == 0) {
+    if (N == 0) {
+      k_fill_i32<<<nblk(G + 1, 256), 256, 0, st>>>(edge_graph_ptr, G + 1, 0);
+      k_fill_i32<<<1, 64, 0, st>>>(colT_ptr, 1, 0);
+      HGNN_LAUNCH_CHECK("k_fill_i32");
+      return HGNN_OK;
+    }
+  }
+  int32_t* key_j = static_cast<int32_t*>(tmp);
+  int32_t* key_c = key_j + E;
+  if (E > 0) {
+    k_neighbors<true><<<nblk((int64_t)N * 64, 256), 256, 0, st>>>(N, pos, w.meta, w.atom_graph, w.atom_bin, w.bin_start,
+                                                                  w.bin_atoms, rc, nullptr, row_ptr, key_j, key_c);
+    HGNN_LAUNCH_CHECK("k_neighbors<fill>");
+    k_emit_rows<<<nblk((int64_t)N * 64, 256), 256, 0, st>>>(N, pos, w.meta, w.atom_graph, row_ptr, key_j, key_c, dst, col,
+                                                            shift, d2, rvec);
+    HGNN_LAUNCH_CHECK("k_emit_rows");
+  }
+  k_edge_graph_ptr<<<nblk(G + 1, 256), 256, 0, st>>>(G, graph_off, row_ptr, edge_graph_ptr);
+  HGNN_LAUNCH_CHECK("k_edge_graph_ptr");
+  // transpose plan
+  k_fill_i32<<<nblk(N, 256), 256, 0, st>>>(w.colT_cnt, N, 0);
+  k_fill_i32<<<nblk(N, 256), 256, 0, st>>>(w.colT_cur, N, 0);
+  HGNN_LAUNCH_CHECK("k_fill_i32");
+  if (E > 0) {
+    k_count_sources<<<nblk(E, 256), 256, 0, st>>>(E, col, w.colT_cnt);
+    HGNN_LAUNCH_CHECK("k_count_sources");
+  }
+  HGNN_TRY(exclusive_scan_i32(st, w.colT_cnt, colT_ptr, N, w.scan));
+  if (E > 0) {
+    int32_t* unsorted = key_j;  // the keys are dead by now
+    k_fill_sources<<<nblk(E, 256), 256, 0, st>>>(E, col, colT_ptr, w.colT_cur, unsorted);
+    HGNN_LAUNCH_CHECK("k_fill_sources");
+    k_rank_sources<<<nblk((int64_t)N * 64, 256), 256, 0, st>>>(N, colT_ptr, unsorted, permT);
+    HGNN_LAUNCH_CHECK("k_rank_sources");
+  }
+  return HGNN_OK;
+}

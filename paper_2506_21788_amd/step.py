@@ -1,0 +1,146 @@
+"""Harness around the binding: owns the device buffers of one batch and issues the library calls of
+one training step in order. No arithmetic happens here -- torch is the allocator and the stream."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from . import binding as B
+
+
+def _dev(a, dtype=None):
+    t = torch.as_tensor(np.ascontiguousarray(a))
+    if dtype is not None:
+        t = t.to(dtype)
+    return t.cuda().contiguous()
+
+
+def _bytes(n):
+    return torch.empty(max(int(n), 16), dtype=torch.uint8, device="cuda")
+
+
+class Graph:
+    """Device-resident radius graph of a batch (destination-sorted CSR + transpose plan)."""
+
+    def __init__(self, pos, graph_off, cell, pbc, rc):
+        self.N = int(pos.shape[0])
+        self.G = int(graph_off.shape[0] - 1)
+        self.rc = float(rc)
+        self.pos, self.graph_off, self.cell, self.pbc = pos, graph_off, cell, pbc
+        self.ws = _bytes(B.radius_graph_workspace_bytes(self.N, self.G))
+        self.row_ptr = torch.empty(self.N + 1, dtype=torch.int32, device="cuda")
+        self.E = None
+
+    def build(self):
+        N, G = self.N, self.G
+        E = B.radius_graph_count(N, G, self.pos, self.graph_off, self.cell, self.pbc, self.rc, self.ws, self.row_ptr)
+        if self.E != E:
+            i32 = dict(dtype=torch.int32, device="cuda")
+            f32 = dict(dtype=torch.float32, device="cuda")
+            self.E = E
+            self.tmp = _bytes(8 * E)
+            self.dst = torch.empty(E, **i32)
+            self.col = torch.empty(E, **i32)
+            self.shift = torch.empty((E, 3), dtype=torch.int8, device="cuda")
+            self.d2 = torch.empty(E, **f32)
+            self.rvec = torch.empty((E, 3), **f32)
+            self.edge_graph_ptr = torch.empty(G + 1, **i32)
+            self.colT_ptr = torch.empty(N + 1, **i32)
+            self.permT = torch.empty(E, **i32)
+        B.radius_graph_fill(N, G, self.pos, self.graph_off, self.cell, self.pbc, self.rc, self.ws, self.tmp,
+                            self.row_ptr, E, self.dst, self.col, self.shift, self.d2, self.rvec,
+                            self.edge_graph_ptr, self.colT_ptr, self.permT)
+        return self
+
+    def to_numpy(self):
+        keys = ("row_ptr", "dst", "col", "shift", "d2", "rvec", "edge_graph_ptr", "colT_ptr", "permT")
+        out = {k: getattr(self, k).cpu().numpy() for k in keys}
+        out["E"] = self.E
+        return out
+
+
+class HotPath:
+    """One GPU's share of a training step on one batch: graph -> embed -> L layers -> pool -> heads,
+    forward and backward. Inputs are numpy arrays (uploaded once); outputs stay on the device."""
+
+    def __init__(self, batch, rc, H, L, S, dtype, emb, layer_weights, head_weights, alpha=None, Hh=None):
+        self.N, self.G, self.H, self.L, self.S = batch.N, batch.G, H, L, S
+        self.Hh = H if Hh is None else Hh
+        self.dtype = {"f32": B.F32, "bf16": B.BF16}[dtype]
+        self.pos = _dev(batch.pos, torch.float32)
+        self.Z = _dev(batch.Z, torch.int32)
+        self.graph_off = _dev(batch.graph_off, torch.int32)
+        self.cell = _dev(batch.cell, torch.float32)
+        self.pbc = _dev(batch.pbc, torch.uint8)
+        self.source_id = _dev(batch.source_id, torch.int32)
+        self.emb = _dev(emb, torch.float32)
+        self.W = [_dev(w, torch.float32) for w in layer_weights]
+        self.Whead = _dev(head_weights, torch.float32)
+        self.alpha = alpha
+        self.graph = Graph(self.pos, self.graph_off, self.cell, self.pbc, rc)
+        self._alloc_E = None
+        self.plan = torch.empty(B.multihead_plan_ints(self.N, self.G, S), dtype=torch.int32, device="cuda")
+        B.multihead_plan(self.N, self.G, S, self.graph_off, self.source_id, self.plan)
+
+    # -- graph ---------------------------------------------------------------------------------
+    def build_graph(self):
+        self.graph.build()
+        if self.alpha is None:
+            self.alpha = 1.0 / max(1.0, self.graph.E / max(1, self.N))
+        self._alloc(self.graph.E)
+        return self.graph
+
+    def _alloc(self, E):
+        if self._alloc_E == E:
+            return
+        N, G, H, L, S = self.N, self.G, self.H, self.L, self.S
+        f32 = dict(dtype=torch.float32, device="cuda")
+        ws_b, saved_b = B.mp_layer_workspace_bytes(N, E, H, self.dtype)
+        hws_b, hsaved_b = B.multihead_decode_workspace_bytes(N, G, H, self.Hh, S, self.dtype)
+        self.ws = _bytes(max(ws_b, hws_b))
+        self.saved = [_bytes(saved_b) for _ in range(L)]
+        self.hsaved = _bytes(hsaved_b)
+        self.h = [torch.empty((N, H), **f32) for _ in range(L + 1)]
+        self.v = [torch.zeros((N, 3), **f32) for _ in range(L + 1)]   # v[0] stays zero: v^0 = 0
+        self.p = torch.empty((G, H), **f32)
+        self.energy = torch.empty(G, **f32)
+        self.force = torch.empty((N, 3), **f32)
+        self.g_p = torch.empty((G, H), **f32)
+        self.g_h = [torch.empty((N, H), **f32) for _ in range(2)]
+        self.g_v = [torch.empty((N, 3), **f32) for _ in range(2)]
+        self.gW = [torch.empty_like(w) for w in self.W]
+        self.gWhead = torch.empty_like(self.Whead)
+        self.g_emb = torch.empty_like(self.emb)
+        self._alloc_E = E
+
+    # -- forward / backward ----------------------------------------------------------------------
+    def forward(self):
+        g, N, G, H = self.graph, self.N, self.G, self.H
+        B.embed_fwd(N, H, self.Z, self.emb, self.h[0])
+        for l in range(self.L):
+            B.mp_layer_fwd(N, g.E, H, self.dtype, self.alpha, g.row_ptr, g.dst, g.col, g.d2, g.rvec,
+                           self.h[l], self.v[l], self.W[l], self.h[l + 1], self.v[l + 1], self.saved[l], self.ws)
+        B.pool_by_graph_fwd(N, G, H, B.POOL_MEAN, self.graph_off, self.h[-1], self.p)
+        B.multihead_decode_fwd(N, G, H, self.Hh, self.S, self.dtype, self.plan, self.p, self.h[-1], self.v[-1],
+                               self.Whead, self.energy, self.force, self.hsaved, self.ws)
+
+    def backward(self, g_energy, g_force):
+        g, N, G, H = self.graph, self.N, self.G, self.H
+        B.multihead_decode_bwd(N, G, H, self.Hh, self.S, self.dtype, self.plan, self.p, self.h[-1], self.v[-1],
+                               self.Whead, self.hsaved, g_energy, g_force, self.g_p, self.g_h[0], self.g_v[0],
+                               self.gWhead, self.ws)
+        B.pool_by_graph_bwd(N, G, H, B.POOL_MEAN, self.graph_off, self.g_p, self.g_h[0], True)
+        cur = 0
+        for l in reversed(range(self.L)):
+            B.mp_layer_bwd(N, g.E, H, self.dtype, self.alpha, g.row_ptr, g.dst, g.col, g.d2, g.rvec, g.colT_ptr,
+                           g.permT, self.h[l], self.W[l], self.saved[l], self.g_h[cur], self.g_v[cur],
+                           self.g_h[1 - cur], self.g_v[1 - cur], self.gW[l], self.ws)
+            cur = 1 - cur
+        B.embed_bwd(N, H, self.Z, self.g_h[cur], self.g_emb)
+        self.g_h0, self.g_v0 = self.g_h[cur], self.g_v[cur]
+
+    def step(self, g_energy, g_force, with_graph=True):
+        if with_graph:
+            self.build_graph()
+        self.forward()
+        self.backward(g_energy, g_force)

@@ -1,0 +1,76 @@
+"""Shared helpers of the GPU parity tests: build a seeded problem, run the oracle, run the library."""
+from __future__ import annotations
+
+import numpy as np
+
+import oracle
+from hgnn_inputs import (init_embedding, init_head_weights, init_layer_weights, make_config,
+                         upstream_grads)
+
+TOL = {  # norm-wise L-inf relative error (max|a-b| / max|b|) against the float64 oracle
+    "f32": dict(fwd=1e-5, grad=1e-4),
+    "bf16": dict(fwd=2e-2, grad=2e-2),
+}
+
+
+def relerr(a, b):
+    a = np.asarray(a, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    assert a.shape == b.shape, (a.shape, b.shape)
+    if b.size == 0:
+        return 0.0
+    den = np.max(np.abs(b))
+    num = np.max(np.abs(a - b))
+    return float(num / den) if den > 0 else float(num)
+
+
+def make_weights(seed, H, L, S, N, G):
+    ss = np.random.SeedSequence(seed).spawn(3)
+    rw = np.random.default_rng(ss[1])
+    rg = np.random.default_rng(ss[2])
+    emb = init_embedding(rw, H)
+    Ws = [init_layer_weights(rw, H) for _ in range(L)]
+    Wh = init_head_weights(rw, H, H, S)
+    gE, gF = upstream_grads(rg, G, N)
+    return emb, Ws, Wh, gE, gF
+
+
+def problem_from_config(name, **over):
+    batch, hp = make_config(name, **over)
+    emb, Ws, Wh, gE, gF = make_weights(hp["seed"], hp["H"], hp["L"], hp["S"], batch.N, batch.G)
+    return dict(batch=batch, hp=hp, emb=emb, Ws=Ws, Wh=Wh, gE=gE, gF=gF)
+
+
+def problem_from_batch(batch, rc, H, L, S, dtype, seed=0):
+    emb, Ws, Wh, gE, gF = make_weights(seed, H, L, S, batch.N, batch.G)
+    hp = dict(rc=rc, H=H, L=L, S=S, dtype=dtype, seed=seed, name="custom")
+    return dict(batch=batch, hp=hp, emb=emb, Ws=Ws, Wh=Wh, gE=gE, gF=gF)
+
+
+def oracle_graph(P):
+    b, hp = P["batch"], P["hp"]
+    return oracle.radius_graph(b.pos, b.graph_off, b.cell, b.pbc, hp["rc"])
+
+
+def oracle_step(P, graph, alpha, grads=True, keep_layers=False):
+    b, hp = P["batch"], P["hp"]
+    return oracle.step_fwd_bwd(b.Z, b.graph_off, b.source_id, graph, P["emb"].astype(np.float64),
+                               [w.astype(np.float64) for w in P["Ws"]], P["Wh"].astype(np.float64),
+                               hp["H"], hp["S"], alpha,
+                               P["gE"].astype(np.float64) if grads else None,
+                               P["gF"].astype(np.float64) if grads else None, keep_layers=keep_layers)
+
+
+def gpu_hotpath(P, alpha=None):
+    from paper_2506_21788_amd.step import HotPath
+    b, hp = P["batch"], P["hp"]
+    return HotPath(b, hp["rc"], hp["H"], hp["L"], hp["S"], hp["dtype"], P["emb"], P["Ws"], P["Wh"], alpha=alpha)
+
+
+def assert_graph_equal(got, want):
+    assert got["E"] == want["E"], (got["E"], want["E"])
+    for k in ("row_ptr", "dst", "col", "shift", "edge_graph_ptr", "colT_ptr", "permT"):
+        assert np.array_equal(got[k], want[k]), k
+    # float outputs are produced by the same individually rounded float32 operations: bit-exact
+    assert np.array_equal(got["d2"].view(np.uint32), want["d2"].view(np.uint32)), "d2"
+    assert np.array_equal(got["rvec"].view(np.uint32), want["rvec"].view(np.uint32)), "rvec"

@@ -1,0 +1,67 @@
+"""The C-ABI library loads and exports every symbol the public header declares (no GPU needed)."""
+import ctypes
+import os
+import re
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "hgnn.h")
+LIB = os.path.join(ROOT, "paper_2506_21788_amd", "libhgnn.so")
+
+
+def declared_symbols():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(hgnn_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_declares_the_boundary():
+    names = declared_symbols()
+    for must in ("hgnn_radius_graph_count", "hgnn_radius_graph_fill", "hgnn_mp_layer_fwd", "hgnn_mp_layer_bwd",
+                 "hgnn_pool_by_graph_fwd", "hgnn_pool_by_graph_bwd", "hgnn_multihead_decode_fwd",
+                 "hgnn_multihead_decode_bwd", "hgnn_multihead_plan", "hgnn_embed_fwd", "hgnn_embed_bwd"):
+        assert must in names
+
+
+def test_library_exports_every_declared_symbol():
+    assert os.path.exists(LIB), "build the library first: python -c 'import __graft_entry__ as g; g.build()'"
+    lib = ctypes.CDLL(LIB)
+    for name in declared_symbols():
+        assert hasattr(lib, name), name
+    lib.hgnn_version.restype = ctypes.c_int32
+    assert lib.hgnn_version() >= 1
+
+
+def test_binding_names_match_the_header():
+    import importlib.util
+    spec = importlib.util.find_spec("paper_2506_21788_amd.binding")
+    src = open(spec.origin).read()
+    for name in declared_symbols():
+        assert f'"{name}"' in src, name
+
+
+def test_host_side_argument_checks_need_no_gpu():
+    lib = ctypes.CDLL(LIB)
+    lib.hgnn_last_error_string.restype = ctypes.c_char_p
+    b = ctypes.c_size_t(0)
+    assert lib.hgnn_radius_graph_workspace_bytes(ctypes.c_int32(100), ctypes.c_int32(3), ctypes.byref(b)) == 0
+    assert b.value > 0
+    assert lib.hgnn_radius_graph_workspace_bytes(ctypes.c_int32(-1), ctypes.c_int32(3), ctypes.byref(b)) == -2
+    a, s = ctypes.c_size_t(0), ctypes.c_size_t(0)
+    # H outside the supported tile granularity
+    rc = lib.hgnn_mp_layer_workspace_bytes(ctypes.c_int32(10), ctypes.c_int64(50), ctypes.c_int32(100),
+                                           ctypes.c_int32(0), ctypes.byref(a), ctypes.byref(s))
+    assert rc == -2 and b"64, 128 or 256" in lib.hgnn_last_error_string()
+    rc = lib.hgnn_mp_layer_workspace_bytes(ctypes.c_int32(10), ctypes.c_int64(50), ctypes.c_int32(128),
+                                           ctypes.c_int32(1), ctypes.byref(a), ctypes.byref(s))
+    assert rc == 0 and a.value > 0 and s.value >= 50 * 128 * 4
+    # edge count that does not fit int32
+    rc = lib.hgnn_mp_layer_workspace_bytes(ctypes.c_int32(10), ctypes.c_int64(2 ** 31), ctypes.c_int32(128),
+                                           ctypes.c_int32(0), ctypes.byref(a), ctypes.byref(s))
+    assert rc == -7
+    # head width must equal H
+    rc = lib.hgnn_multihead_decode_workspace_bytes(ctypes.c_int32(10), ctypes.c_int32(2), ctypes.c_int32(128),
+                                                   ctypes.c_int32(64), ctypes.c_int32(2), ctypes.c_int32(0),
+                                                   ctypes.byref(a), ctypes.byref(s))
+    assert rc == -2
+    lib.hgnn_multihead_plan_ints.restype = ctypes.c_int64
+    assert lib.hgnn_multihead_plan_ints(ctypes.c_int32(7), ctypes.c_int32(3), ctypes.c_int32(2)) >= 2 * 3 + 7 + 3 + 3

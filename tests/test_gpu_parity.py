@@ -1,0 +1,365 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle on the same seeded inputs."""
+import sys
+
+import numpy as np
+import pytest
+
+import oracle
+from hgnn_inputs import concat_graphs, make_config, small_mixed_batch
+from hgnn_inputs.structures import make_crystal, make_cubic_bulk
+
+from parity_util import (TOL, assert_graph_equal, gpu_hotpath, oracle_graph, oracle_step,
+                         problem_from_batch, problem_from_config, relerr)
+
+pytestmark = pytest.mark.gpu
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+def gpu_graph(batch, rc):
+    import torch
+    from paper_2506_21788_amd.step import Graph, _dev
+    g = Graph(_dev(batch.pos, torch.float32), _dev(batch.graph_off, torch.int32), _dev(batch.cell, torch.float32),
+              _dev(batch.pbc, torch.uint8), rc)
+    g.build()
+    torch.cuda.synchronize()
+    return g
+
+
+# ------------------------------------------------------------------------------------------------
+# radius graph: bit-exact
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("seed,rc", [(0, 5.0), (1, 4.0), (2, 6.0), (5, 3.0)])
+def test_radius_graph_small_mixed(seed, rc):
+    say("radius graph small mixed", seed, rc)
+    b = small_mixed_batch(seed, n_mol=4, n_cry=4)
+    want = oracle.radius_graph(b.pos, b.graph_off, b.cell, b.pbc, rc)
+    got = gpu_graph(b, rc).to_numpy()
+    assert_graph_equal(got, want)
+    assert want["E"] > 100
+
+
+@pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg3"])
+def test_radius_graph_configs(name):
+    say("radius graph", name)
+    b, hp = make_config(name)
+    want = oracle.radius_graph(b.pos, b.graph_off, b.cell, b.pbc, hp["rc"])
+    got = gpu_graph(b, hp["rc"]).to_numpy()
+    assert_graph_equal(got, want)
+
+
+def test_radius_graph_edge_cases():
+    say("radius graph edge cases")
+    # single atoms, an isolated atom, an empty graph in the middle, a one-atom periodic cell
+    pos1 = np.array([[0.0, 0, 0]], np.float32)
+    mol = (np.array([[0, 0, 0], [1.0, 0, 0], [40.0, 0, 0]], np.float32), np.array([1, 6, 8], np.int32))
+    cry = (pos1, np.array([3], np.int32), (np.eye(3) * 2.0).astype(np.float32))
+    empty = (np.zeros((0, 3), np.float32), np.zeros(0, np.int32))
+    b = concat_graphs([(pos1, np.array([1], np.int32)), mol, empty, cry, empty])
+    for rc in (1.5, 2.0, 2.0001, 4.5):
+        want = oracle.radius_graph(b.pos, b.graph_off, b.cell, b.pbc, rc)
+        got = gpu_graph(b, rc).to_numpy()
+        assert_graph_equal(got, want)
+    # no atoms at all
+    b0 = concat_graphs([empty])
+    got = gpu_graph(b0, 3.0).to_numpy()
+    assert got["E"] == 0 and got["row_ptr"].tolist() == [0]
+
+
+def test_radius_graph_long_rows_and_many_images():
+    """A dense small cell: rows of several hundred edges, up to 5 images per direction."""
+    say("radius graph long rows")
+    rng = np.random.default_rng(3)
+    graphs = [make_crystal(rng, 12, 2.5, 3.5, 0.8, 1, 50, max_density=0.5) for _ in range(3)]
+    b = concat_graphs(graphs)
+    rc = 7.0
+    want = oracle.radius_graph(b.pos, b.graph_off, b.cell, b.pbc, rc)
+    assert np.diff(want["row_ptr"]).max() > 256
+    got = gpu_graph(b, rc).to_numpy()
+    assert_graph_equal(got, want)
+
+
+def test_radius_graph_full_size_cfg5_sampled_rows():
+    """Config 5 at its real size (4 x 20,000 atoms): every row pointer checked through sampled rows
+    that the oracle computes one by one; global invariants checked everywhere."""
+    say("radius graph cfg5 full size")
+    b, hp = make_config("cfg5")
+    g = gpu_graph(b, hp["rc"]).to_numpy()
+    N = b.N
+    deg = np.diff(g["row_ptr"])
+    assert g["row_ptr"][0] == 0 and g["row_ptr"][-1] == g["E"]
+    assert 85 < deg.mean() < 95
+    rng = np.random.default_rng(0)
+    rows = np.sort(rng.choice(N, size=64, replace=False))
+    per = oracle.radius_graph_rows(b.pos, b.graph_off, b.cell, b.pbc, hp["rc"], rows)
+    for i, (col, shift, d2, rvec) in zip(rows, per):
+        e0, e1 = g["row_ptr"][i], g["row_ptr"][i + 1]
+        assert np.array_equal(g["col"][e0:e1], col), i
+        assert np.array_equal(g["shift"][e0:e1], shift), i
+        assert np.array_equal(g["d2"][e0:e1].view(np.uint32), d2.view(np.uint32)), i
+        assert np.array_equal(g["rvec"][e0:e1].view(np.uint32), rvec.view(np.uint32)), i
+        assert np.all(g["dst"][e0:e1] == i)
+    # invariants at any size
+    assert np.array_equal(g["dst"], np.repeat(np.arange(N, dtype=np.int32), deg))
+    key = g["dst"].astype(np.int64) * N + g["col"]
+    assert np.all(np.diff(key) >= 0)
+    ct, pt = oracle.transpose_plan(g["col"], N)
+    assert np.array_equal(ct, g["colT_ptr"]) and np.array_equal(pt, g["permT"])
+    assert np.array_equal(g["edge_graph_ptr"], g["row_ptr"][b.graph_off])
+
+
+def test_radius_graph_error_paths():
+    say("radius graph error paths")
+    import torch
+    from paper_2506_21788_amd import binding as B
+    from paper_2506_21788_amd.step import _dev
+    b = small_mixed_batch(0)
+    N, G = b.N, b.G
+    pos, cell, pbc = _dev(b.pos, torch.float32), _dev(b.cell, torch.float32), _dev(b.pbc, torch.uint8)
+    ws = torch.empty(B.radius_graph_workspace_bytes(N, G), dtype=torch.uint8, device="cuda")
+    row_ptr = torch.empty(N + 1, dtype=torch.int32, device="cuda")
+    off = b.graph_off.copy()
+    off[1], off[2] = off[2], off[1]
+    if off[1] == off[2]:
+        off[1] += 1
+    with pytest.raises(B.HgnnError) as e:
+        B.radius_graph_count(N, G, pos, _dev(off, torch.int32), cell, pbc, 4.0, ws, row_ptr)
+    assert e.value.code == -3
+    off = b.graph_off.copy()
+    off[0] = 1
+    with pytest.raises(B.HgnnError) as e:
+        B.radius_graph_count(N, G, pos, _dev(off, torch.int32), cell, pbc, 4.0, ws, row_ptr)
+    assert e.value.code == -3
+    bad = b.cell.copy()
+    gi = int(np.nonzero(b.pbc)[0][0])
+    bad[gi][2] = bad[gi][1]
+    with pytest.raises(B.HgnnError) as e:
+        B.radius_graph_count(N, G, pos, _dev(b.graph_off, torch.int32), _dev(bad, torch.float32), pbc, 4.0, ws, row_ptr)
+    assert e.value.code == -4
+    with pytest.raises(B.HgnnError) as e:
+        B.radius_graph_count(N, G, pos, _dev(b.graph_off, torch.int32), cell, pbc, -1.0, ws, row_ptr)
+    assert e.value.code == -2
+    with pytest.raises(B.HgnnError) as e:
+        B.radius_graph_count(N, G, pos, _dev(b.graph_off, torch.int32), cell, pbc, 4.0, ws[:64], row_ptr)
+    assert e.value.code == -6
+    with pytest.raises(B.HgnnError) as e:
+        B.radius_graph_count(N, G, None, _dev(b.graph_off, torch.int32), cell, pbc, 4.0, ws, row_ptr)
+    assert e.value.code == -1
+    # the good call still works afterwards
+    assert B.radius_graph_count(N, G, pos, _dev(b.graph_off, torch.int32), cell, pbc, 4.0, ws, row_ptr) > 0
+
+
+# ------------------------------------------------------------------------------------------------
+# whole step against the oracle
+# ------------------------------------------------------------------------------------------------
+def compare_step(P, tag, check_graph=True):
+    import torch
+    hp = P["hp"]
+    tol = TOL[hp["dtype"]]
+    og = oracle_graph(P)
+    hpth = gpu_hotpath(P)
+    hpth.build_graph()
+    torch.cuda.synchronize()
+    if check_graph:
+        assert_graph_equal(hpth.graph.to_numpy(), og)
+    alpha = hpth.alpha
+    want = oracle_step(P, og, alpha, keep_layers=True)
+    gE = torch.as_tensor(P["gE"]).cuda()
+    gF = torch.as_tensor(P["gF"]).cuda()
+    hpth.forward()
+    hpth.backward(gE, gF)
+    torch.cuda.synchronize()
+    errs = {}
+    for l in range(1, hp["L"] + 1):
+        errs[f"h{l}"] = relerr(hpth.h[l].cpu().numpy(), want["hs"][l])
+    errs["v"] = relerr(hpth.v[-1].cpu().numpy(), want["v"])
+    errs["p"] = relerr(hpth.p.cpu().numpy(), want["p"])
+    errs["energy"] = relerr(hpth.energy.cpu().numpy(), want["energy"])
+    errs["force"] = relerr(hpth.force.cpu().numpy(), want["force"])
+    gerrs = {"g_emb": relerr(hpth.g_emb.cpu().numpy(), want["g_emb"]),
+             "g_heads": relerr(hpth.gWhead.cpu().numpy(), want["g_heads"]),
+             "g_h0": relerr(hpth.g_h0.cpu().numpy(), want["g_h0"]),
+             "g_v0": relerr(hpth.g_v0.cpu().numpy(), want["g_v0"])}
+    from hgnn_inputs import layer_field_slices
+    sl = layer_field_slices(hp["H"])
+    for l in range(hp["L"]):
+        got = hpth.gW[l].cpu().numpy()
+        for name, (lo, hi, _) in sl.items():
+            gerrs[f"gW{l}.{name}"] = relerr(got[lo:hi], want["g_layers"][l][lo:hi])
+    say(tag, "N", P["batch"].N, "E", og["E"], "fwd", {k: f"{v:.2e}" for k, v in errs.items()})
+    say(tag, "grad", {k: f"{v:.2e}" for k, v in gerrs.items()})
+    for k, v in errs.items():
+        assert v <= tol["fwd"], (tag, k, v)
+    for k, v in gerrs.items():
+        assert v <= tol["grad"], (tag, k, v)
+    return hpth, want
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("H", [64, 128, 256])
+def test_step_small_mixed(H, dtype):
+    say("step small mixed", H, dtype)
+    b = small_mixed_batch(7, n_mol=5, n_cry=4, S=3, mol_atoms=(3, 40), cry_atoms=(2, 30))
+    P = problem_from_batch(b, 4.5, H, 2, 3, dtype, seed=H)
+    compare_step(P, f"small H={H} {dtype}")
+
+
+def test_step_cfg1():
+    say("step cfg1")
+    compare_step(problem_from_config("cfg1"), "cfg1")
+
+
+def test_step_cfg2():
+    say("step cfg2")
+    hpth, want = compare_step(problem_from_config("cfg2"), "cfg2")
+    # routing plan is integer work: bit-exact
+    from paper_2506_21788_amd import binding as B
+    P = problem_from_config("cfg2")
+    b = P["batch"]
+    f = B.plan_fields(hpth.plan.cpu(), b.N, b.G, 5)
+    ggp, gperm, gap, aperm = oracle.routing_plan(b.source_id, b.graph_off, 5)
+    assert np.array_equal(f["grp_graph_ptr"].numpy(), ggp) and np.array_equal(f["graph_perm"].numpy(), gperm)
+    assert np.array_equal(f["grp_atom_ptr"].numpy(), gap) and np.array_equal(f["atom_perm"].numpy(), aperm)
+
+
+def test_step_cfg3_bf16():
+    say("step cfg3")
+    compare_step(problem_from_config("cfg3"), "cfg3")
+
+
+def test_step_isolated_atoms_and_absent_source():
+    """Rows with no edge (M = 0, v unchanged), a graph without any edge, a source with no graph."""
+    say("step isolated/absent")
+    import torch
+    mol = (np.array([[0, 0, 0], [1.2, 0, 0], [40.0, 0, 0], [0, 1.1, 0.3]], np.float32), np.array([1, 6, 8, 7], np.int32))
+    lone = (np.array([[0, 0, 0], [30.0, 0, 0]], np.float32), np.array([1, 1], np.int32))
+    rng = np.random.default_rng(1)
+    cry = make_crystal(rng, 6, 3.0, 5.0, 0.9, 1, 30, max_density=0.2)
+    b = concat_graphs([mol, lone, cry], np.array([0, 3, 3], np.int32))
+    P = problem_from_batch(b, 3.0, 64, 2, 4, "f32", seed=5)
+    hpth, want = compare_step(P, "isolated")
+    from hgnn_inputs import head_weight_count
+    per = head_weight_count(64, 64)
+    gh = hpth.gWhead.cpu().numpy()
+    assert np.all(gh[per:3 * per] == 0.0) and np.any(gh[:per] != 0.0) and np.any(gh[3 * per:] != 0.0)
+
+
+def test_step_is_bitwise_reproducible():
+    say("step reproducible")
+    import torch
+    P = problem_from_config("cfg2")
+    outs = []
+    for _ in range(2):
+        hpth = gpu_hotpath(P)
+        hpth.build_graph()
+        hpth.forward()
+        hpth.backward(torch.as_tensor(P["gE"]).cuda(), torch.as_tensor(P["gF"]).cuda())
+        torch.cuda.synchronize()
+        outs.append([t.cpu().numpy().copy() for t in (hpth.energy, hpth.force, hpth.gWhead, hpth.g_emb, *hpth.gW)])
+    for a, c in zip(*outs):
+        assert np.array_equal(a.view(np.uint32), c.view(np.uint32))
+
+
+# ------------------------------------------------------------------------------------------------
+# full sizes, in the launch configuration bench.py times
+# ------------------------------------------------------------------------------------------------
+def sub_batch(b, graphs):
+    gl = [(b.pos[b.graph_off[g]:b.graph_off[g + 1]], b.Z[b.graph_off[g]:b.graph_off[g + 1]],
+           b.cell[g] if b.pbc[g] else None) for g in graphs]
+    return concat_graphs(gl, b.source_id[graphs])
+
+
+def test_full_size_cfg4_sampled_graphs():
+    """Config 4 (~40k atoms, ~1.2M edges, bf16, 5 sources). A graph's outputs depend on that graph
+    only, so the oracle recomputes sampled graphs one sub-batch at a time."""
+    say("cfg4 full size")
+    import torch
+    P = problem_from_config("cfg4")
+    b, hp = P["batch"], P["hp"]
+    hpth = gpu_hotpath(P)
+    hpth.build_graph()
+    hpth.forward()
+    hpth.backward(torch.as_tensor(P["gE"]).cuda(), torch.as_tensor(P["gF"]).cuda())
+    torch.cuda.synchronize()
+    say("cfg4 N", b.N, "G", b.G, "E", hpth.graph.E, "alpha", hpth.alpha)
+    assert 0.8e6 < hpth.graph.E < 1.6e6
+    rng = np.random.default_rng(0)
+    graphs = np.sort(rng.choice(b.G, size=24, replace=False))
+    sb = sub_batch(b, graphs)
+    atoms = np.concatenate([np.arange(b.graph_off[g], b.graph_off[g + 1]) for g in graphs])
+    Ps = dict(P, batch=sb, gE=P["gE"][graphs], gF=P["gF"][atoms])
+    og = oracle_graph(Ps)
+    # edges of the sampled graphs, bit-exact
+    G = hpth.graph.to_numpy()
+    for k, g in enumerate(graphs):
+        e0, e1 = G["edge_graph_ptr"][g], G["edge_graph_ptr"][g + 1]
+        o0, o1 = og["edge_graph_ptr"][k], og["edge_graph_ptr"][k + 1]
+        assert e1 - e0 == o1 - o0
+        assert np.array_equal(G["col"][e0:e1] - b.graph_off[g], og["col"][o0:o1] - sb.graph_off[k])
+        assert np.array_equal(G["shift"][e0:e1], og["shift"][o0:o1])
+        assert np.array_equal(G["d2"][e0:e1].view(np.uint32), og["d2"][o0:o1].view(np.uint32))
+    want = oracle_step(Ps, og, hpth.alpha)
+    tol = TOL["bf16"]
+    errs = dict(energy=relerr(hpth.energy.cpu().numpy()[graphs], want["energy"]),
+                force=relerr(hpth.force.cpu().numpy()[atoms], want["force"]),
+                h=relerr(hpth.h[-1].cpu().numpy()[atoms], want["h"]),
+                g_h0=relerr(hpth.g_h0.cpu().numpy()[atoms], want["g_h0"]))
+    say("cfg4 sampled", {k: f"{v:.2e}" for k, v in errs.items()})
+    assert errs["energy"] <= tol["fwd"] and errs["force"] <= tol["fwd"] and errs["h"] <= tol["fwd"]
+    assert errs["g_h0"] <= tol["grad"]
+    for t in (hpth.gWhead, hpth.g_emb, *hpth.gW):
+        assert bool(torch.isfinite(t).all())
+
+
+def test_full_size_cfg5_layerwise_sampled_rows():
+    """Config 5 (80,000 atoms, ~7M edges, fp32). Row i of a layer's output depends on h (all rows)
+    and the edges of row i only; the oracle recomputes sampled rows of every layer from the
+    library's own layer input."""
+    say("cfg5 full size")
+    import torch
+    P = problem_from_config("cfg5")
+    b, hp = P["batch"], P["hp"]
+    hpth = gpu_hotpath(P)
+    hpth.build_graph()
+    hpth.forward()
+    hpth.backward(torch.as_tensor(P["gE"]).cuda(), torch.as_tensor(P["gF"]).cuda())
+    torch.cuda.synchronize()
+    E = hpth.graph.E
+    say("cfg5 E", E, "alpha", hpth.alpha)
+    assert 6.5e6 < E < 8e6
+    G = hpth.graph.to_numpy()
+    rng = np.random.default_rng(1)
+    rows = np.sort(rng.choice(b.N, size=200, replace=False))
+    sel = np.concatenate([np.arange(G["row_ptr"][i], G["row_ptr"][i + 1]) for i in rows])
+    tol = TOL["f32"]
+    for l in range(hp["L"]):
+        h_in = hpth.h[l].cpu().numpy().astype(np.float64)
+        v_in = hpth.v[l].cpu().numpy().astype(np.float64)
+        h_out, v_out, _ = oracle.mp_layer_fwd(h_in, v_in, G["dst"][sel], G["col"][sel], G["d2"][sel], G["rvec"][sel],
+                                              P["Ws"][l].astype(np.float64), hpth.alpha)
+        eh = relerr(hpth.h[l + 1].cpu().numpy()[rows], h_out[rows])
+        ev = relerr(hpth.v[l + 1].cpu().numpy()[rows], v_out[rows])
+        say("cfg5 layer", l, f"h {eh:.2e} v {ev:.2e}")
+        assert eh <= tol["fwd"] and ev <= tol["fwd"]
+    # heads on the library's own last-layer features
+    p = oracle.pool_fwd(hpth.h[-1].cpu().numpy(), b.graph_off)
+    e, f, _ = oracle.heads_fwd(p, hpth.h[-1].cpu().numpy(), hpth.v[-1].cpu().numpy(), b.graph_off, b.source_id,
+                               P["Wh"].astype(np.float64), hp["H"], hp["S"])
+    assert relerr(hpth.p.cpu().numpy(), p) <= tol["fwd"]
+    assert relerr(hpth.energy.cpu().numpy(), e) <= tol["fwd"]
+    assert relerr(hpth.force.cpu().numpy(), f) <= tol["fwd"]
+    for t in (hpth.gWhead, hpth.g_emb, *hpth.gW):
+        assert bool(torch.isfinite(t).all())
+
+
+def test_reduced_cfg5_backward():
+    """Same density, cutoff, width and depth as config 5 on a cell the oracle can differentiate."""
+    say("cfg5 reduced")
+    rng = np.random.default_rng(0)
+    graphs = [make_cubic_bulk(rng, 1500, 0.1, 1.0, 1, 30) for _ in range(2)]
+    b = concat_graphs(graphs)
+    P = problem_from_batch(b, 6.0, 128, 3, 1, "f32", seed=3)
+    compare_step(P, "cfg5-reduced")
