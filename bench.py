@@ -1,0 +1,177 @@
+#!/usr/bin/env python3
+"""Benchmark of the hot path on one MI355X.
+
+A step = one pass of the whole path over one synthetic batch that already sits in HBM: radius graph,
+embedding, L message-passing layers, pooling, per-source heads, and the reverse pass of all of them.
+Prints ONE JSON line. Default workload: config 4 (mixed five-source batch, ~40k atoms, ~1.2M edges,
+H=256, 6 layers, bf16 matrix-core operands).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+PEAK_HBM_GBS = 8000.0
+PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
+
+
+def kernel_work(tag, N, E, H, dtype):
+    """Algorithmic work of ONE launch of a kernel class: ('mfma', flops) or ('hbm', bytes)."""
+    f = 4
+    if tag in ("gemm_edge", "wgrad_edge"):
+        return "mfma", 2.0 * E * H * H
+    if tag == "edge_fused_fwd":
+        return "mfma", 2.0 * E * H * H
+    if tag == "edge_fused_bwd":
+        return "mfma", 4.0 * E * H * H
+    if tag == "seg_fwd":
+        return "hbm", E * (H + 3) * f + (N + 1) * 4 + N * (H + 3) * f
+    if tag in ("segsum_dst", "segsum_src"):
+        return "hbm", E * H * f + N * H * f + (N + 1) * 4 + (4 * E if tag == "segsum_src" else 0)
+    if tag == "edge_pre":
+        return "hbm", E * H * f + 12 * E + N * 2 * H * f
+    if tag == "edge_gz2":
+        return "hbm", 2 * E * H * f + 16 * E + N * H * f
+    if tag == "colsum":
+        return "hbm", E * H * f
+    if tag in ("neigh_count", "neigh_fill", "neigh_emit", "neigh_transpose", "neigh_setup"):
+        return "hbm", 12 * N + 27 * E + 8 * N
+    return "hbm", 0.0
+
+
+def cpu_baseline(P, target_edges=30000):
+    """The oracle, as it stands, on a bounded sample (the first graphs of the same batch)."""
+    import numpy as np
+    import oracle
+    from parity_util import oracle_graph, oracle_step, sub_batch
+    b = P["batch"]
+    # grow the sample until the oracle graph has about target_edges edges (degree estimate ~30)
+    k, atoms = 0, 0
+    while k < b.G and atoms < target_edges / 30.0:
+        atoms += int(b.graph_off[k + 1] - b.graph_off[k])
+        k += 1
+    graphs = np.arange(k)
+    sb = sub_batch(b, graphs)
+    Ps = dict(P, batch=sb, gE=P["gE"][:k], gF=P["gF"][:sb.N])
+    t0 = time.perf_counter()
+    og = oracle_graph(Ps)
+    alpha = 1.0 / max(1.0, og["E"] / sb.N)
+    oracle_step(Ps, og, alpha)
+    dt = time.perf_counter() - t0
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([d.get("num_threads", 1) for d in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    return {"value": og["E"] / dt, "unit": "edges/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"first {k} graphs of the batch ({sb.N} atoms, {og['E']} edges), numpy float64, "
+                      f"graph + fwd + bwd, {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", default="cfg4")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--breakdown", action="store_true", help="print the per-kernel-class split to stderr")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; no figure at several GPUs exists (--gpus 1 only)",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from parity_util import gpu_hotpath, problem_from_config
+    from paper_2506_21788_amd import binding as B
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    P = problem_from_config(args.config)
+    b, hp = P["batch"], P["hp"]
+    hot = gpu_hotpath(P)
+    gE = torch.as_tensor(P["gE"]).cuda()
+    gF = torch.as_tensor(P["gF"]).cuda()
+
+    for _ in range(max(1, args.warmup)):
+        hot.step(gE, gF)
+    torch.cuda.synchronize()
+    E, N, G, H, L = hot.graph.E, b.N, b.G, hp["H"], hp["L"]
+
+    # which kernel class dominates? (all classes timed over two untimed steps)
+    ntags = B.profile_num_tags()
+    B.profile_begin((1 << ntags) - 1)
+    for _ in range(2):
+        hot.step(gE, gF)
+    B.profile_end()
+    split = {}
+    for t in range(ntags):
+        n, ms = B.profile_read(t)
+        if n:
+            split[B.profile_tag_name(t)] = {"launches_per_step": n / 2, "ms_per_step": ms / 2}
+    dom = max(split, key=lambda k: split[k]["ms_per_step"])
+    dom_id = [t for t in range(ntags) if B.profile_tag_name(t) == dom][0]
+
+    # timed region: whole steps, with HIP events around the dominant kernel class only
+    B.profile_begin(1 << dom_id)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        hot.step(gE, gF)
+    torch.cuda.synchronize()
+    t_full = (time.perf_counter() - t0) / args.steps
+    B.profile_end()
+    dom_n, dom_ms = B.profile_read(dom_id)
+
+    # message passing only (graph prebuilt), for reference
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        hot.step(gE, gF, with_graph=False)
+    torch.cuda.synchronize()
+    t_mp = (time.perf_counter() - t0) / args.steps
+
+    bound, work = kernel_work(dom, N, E, H, hp["dtype"])
+    avg_s = dom_ms / max(dom_n, 1) * 1e-3
+    if bound == "mfma":
+        peak, unit, ach = PEAK_TFLOPS[hp["dtype"]], "TFLOP/s", work / avg_s / 1e12
+    else:
+        peak, unit, ach = PEAK_HBM_GBS, "GB/s", work / avg_s / 1e9
+    roofline = {"kernel": dom, "bound": bound, "achieved": ach, "peak": peak, "unit": unit, "frac": ach / peak,
+                "traffic": None, "avg_launch_ms": avg_s * 1e3, "launches_per_step": dom_n / args.steps,
+                "work_per_launch": work}
+
+    out = {
+        "metric": "message-passing edges/s (fwd+bwd), whole step incl. neighbour search, 1 MI355X",
+        "value": E / t_full, "unit": "edges/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": t_full * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": hp["dtype"], "data": "synthetic",
+        "config": {"workload": f"{args.config}: {hp['desc']}", "atoms": N, "graphs": G, "edges": E, "H": H,
+                   "layers": L, "sources": hp["S"], "cutoff": hp["rc"], "alpha": hot.alpha},
+        "edge_layers_per_s": E * L / t_full, "graphs_per_s": G / t_full,
+        "ms_per_step_graph_prebuilt": t_mp * 1e3, "edges_per_s_graph_prebuilt": E / t_mp,
+        "roofline": roofline,
+        "kernel_split_ms_per_step": {k: round(v["ms_per_step"], 4) for k, v in
+                                     sorted(split.items(), key=lambda kv: -kv[1]["ms_per_step"])},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(P)
+    if args.breakdown:
+        for k, v in sorted(split.items(), key=lambda kv: -kv[1]["ms_per_step"]):
+            bd, w = kernel_work(k, N, E, H, hp["dtype"])
+            per = v["ms_per_step"] / v["launches_per_step"] * 1e-3
+            rate = (w / per / 1e12, "TFLOP/s") if bd == "mfma" else (w / per / 1e9, "GB/s")
+            print(f"{k:18s} {v['launches_per_step']:6.1f} launches  {v['ms_per_step']:9.3f} ms/step  "
+                  f"{rate[0]:10.1f} {rate[1]}", file=sys.stderr)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

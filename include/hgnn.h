@@ -188,6 +188,19 @@ int32_t hgnn_multihead_decode_bwd(void* stream, int32_t N, int32_t G, int32_t H,
                                   float* g_v /*out [N,3]*/, float* gWhead /*out*/,
                                   void* ws, size_t ws_bytes);
 
+/* ---------------------------------------------------------------------------------------------
+ * Instrumentation (for benchmarks; not part of the method): time classes of kernels with HIP events
+ * recorded on the launch stream. _begin enables the classes whose bit is set in tag_mask and clears
+ * earlier records; _end SYNCHRONISES the stream and accumulates; _read returns how many launches of
+ * a class were timed and their total duration. Not thread safe; costs two event records per timed
+ * launch and nothing for classes that are not enabled.
+ * ------------------------------------------------------------------------------------------- */
+int32_t hgnn_profile_begin(uint64_t tag_mask);
+int32_t hgnn_profile_end(void* stream);
+int32_t hgnn_profile_num_tags(void);
+const char* hgnn_profile_tag_name(int32_t tag);
+int32_t hgnn_profile_read(int32_t tag, int64_t* launches_host, double* total_ms_host);
+
 #ifdef __cplusplus
 }
 #endif

@@ -24,6 +24,8 @@ EXPORTS = [
     "hgnn_pool_by_graph_fwd", "hgnn_pool_by_graph_bwd",
     "hgnn_multihead_plan_ints", "hgnn_multihead_plan",
     "hgnn_multihead_decode_workspace_bytes", "hgnn_multihead_decode_fwd", "hgnn_multihead_decode_bwd",
+    "hgnn_profile_begin", "hgnn_profile_end", "hgnn_profile_num_tags", "hgnn_profile_tag_name",
+    "hgnn_profile_read",
 ]
 
 
@@ -195,3 +197,34 @@ def multihead_decode_bwd(N, G, H, Hh, S, dtype, plan, p, h, v, Whead, saved, g_e
     _check(_dec_bwd(_stream(), N, G, H, Hh, S, dtype, _p(plan), _p(p), _p(h), _p(v), _p(Whead), _p(saved),
                     _nbytes(saved), _p(g_energy), _p(g_force), _p(g_p), _p(g_h), _p(g_v), _p(gWhead), _p(ws),
                     _nbytes(ws)))
+
+
+# ------------------------------------------------------------------------------------------------
+# instrumentation
+_prof_begin = _sig("hgnn_profile_begin", C.c_uint64)
+_prof_end = _sig("hgnn_profile_end", vp)
+_prof_read = _sig("hgnn_profile_read", i32, C.POINTER(i64), C.POINTER(C.c_double))
+_lib.hgnn_profile_tag_name.restype = C.c_char_p
+_lib.hgnn_profile_tag_name.argtypes = [i32]
+
+
+def profile_num_tags():
+    return int(_lib.hgnn_profile_num_tags())
+
+
+def profile_tag_name(tag):
+    return _lib.hgnn_profile_tag_name(tag).decode()
+
+
+def profile_begin(tag_mask):
+    _check(_prof_begin(tag_mask))
+
+
+def profile_end():
+    _check(_prof_end(_stream()))
+
+
+def profile_read(tag):
+    n, ms = i64(0), C.c_double(0.0)
+    _check(_prof_read(tag, C.byref(n), C.byref(ms)))
+    return n.value, ms.value

@@ -35,6 +35,7 @@ int32_t launch_edge_pre(hipStream_t st, int H, int64_t E, const int32_t* dst, co
                         const float* PQ, const float* w1d, float* a1, float* s1) {
   if (E <= 0) return HGNN_OK;
   const int64_t n = E * (H / 4);
+  ProfScope ps(PT_EDGE_PRE, st);
   if (s1) k_edge_pre<true><<<nblk64(n, 256), 256, 0, st>>>(H, E, dst, col, d2, PQ, w1d, a1, s1);
   else k_edge_pre<false><<<nblk64(n, 256), 256, 0, st>>>(H, E, dst, col, d2, PQ, w1d, a1, s1);
   HGNN_LAUNCH_CHECK("k_edge_pre");
@@ -106,6 +107,7 @@ int32_t launch_seg_fwd(hipStream_t st, int H, int N, const int32_t* row_ptr, con
                        const float* wx, float alpha, const float* v_in, float* M, float* v_out) {
   if (N <= 0) return HGNN_OK;
   const unsigned g = nblk64((int64_t)N * 64, 256);
+  ProfScope ps(PT_SEG_FWD, st);
   switch (H) {
     case 64: k_seg_fwd<1><<<g, 256, 0, st>>>(N, row_ptr, z2, rvec, wx, alpha, v_in, M, v_out); break;
     case 128: k_seg_fwd<2><<<g, 256, 0, st>>>(N, row_ptr, z2, rvec, wx, alpha, v_in, M, v_out); break;
@@ -145,6 +147,7 @@ int32_t launch_edge_gz2(hipStream_t st, int H, int64_t E, const int32_t* dst, co
                         float* cvec) {
   if (E <= 0) return HGNN_OK;
   const int64_t n = E * (H / 4);
+  ProfScope ps(PT_EDGE_GZ2, st);
   k_edge_gz2<<<nblk64(n, 256), 256, 0, st>>>(H, E, dst, rvec, z2, gM, ldgM, g_v, wx, alpha, g_z2, cvec);
   HGNN_LAUNCH_CHECK("k_edge_gz2");
   return HGNN_OK;
@@ -181,9 +184,10 @@ k_segsum(int N, const int32_t* __restrict__ ptr, const int32_t* __restrict__ per
 }
 
 int32_t launch_segsum(hipStream_t st, int H, int N, const int32_t* ptr, const int32_t* perm, const float* X,
-                      float* out, int ldo) {
+                      float* out, int ldo, int tag) {
   if (N <= 0) return HGNN_OK;
   const unsigned g = nblk64((int64_t)N * 64, 256);
+  ProfScope ps(tag, st);
   switch (H) {
     case 64: k_segsum<1><<<g, 256, 0, st>>>(N, ptr, perm, X, out, ldo); break;
     case 128: k_segsum<2><<<g, 256, 0, st>>>(N, ptr, perm, X, out, ldo); break;
@@ -201,6 +205,7 @@ __global__ void k_copy_f32(const float* __restrict__ s, float* __restrict__ d, i
 
 int32_t launch_copy_f32(hipStream_t st, const float* src, float* dst, int64_t n) {
   if (n <= 0) return HGNN_OK;
+  ProfScope ps(PT_MISC, st);
   k_copy_f32<<<nblk64(n, 256), 256, 0, st>>>(src, dst, n);
   HGNN_LAUNCH_CHECK("k_copy_f32");
   return HGNN_OK;

@@ -1,0 +1,76 @@
+// Fused per-edge kernels of the message-passing layer (internal).
+//
+// Edge tensors [E,H] that only travel between these kernels are kept in "fragment order": the order
+// in which a wavefront holds a 32-edge x 32-column block in its matrix-core accumulator registers
+// (lane l, register v  <->  edge 8*(v>>2) + 4*(l>>5) + (v&3), column (l&31) of the block). Two
+// variants, both addressed by 32-edge block eb = e/32 and 32-column block cb = n/32:
+//   v-major          ((eb*(H/32) + cb)*16 + v)*64 + l            one element per lane per register
+//   operand-packed   bf16: (((eb*(H/32) + cb)*2 + v/8)*64 + l)*8 + v%8
+//                    fp32: (((eb*(H/32) + cb)*4 + v/4)*64 + l)*4 + v%4
+// The operand-packed form is, unchanged, the A/B operand of the matrix-core instruction that
+// contracts over edges (the weight-gradient product), so that product needs no transpose and no LDS.
+// E is padded to a multiple of 32 in these buffers; padded edges hold zeros where they are summed.
+#pragma once
+
+#include "common.h"
+#include "prof.h"
+
+namespace hgnn {
+
+inline size_t frag_rows(int64_t E) { return (size_t)((E + 31) / 32 * 32); }
+
+struct EdgeFwdArgs {
+  int64_t E;
+  const int32_t *dst, *col;
+  const float* d2;
+  const float* PQ;     // [N,2H]: P = h W1a + b1 | Q = h W1b
+  const float* w1d;    // [H]
+  const void* W2p;     // packed W2 block
+  const float* b2;     // [H]
+  void* a1_pk;         // out: silu(z1), operand-packed (bf16 or fp32)
+  void* z2_vm;         // out: z2, v-major (bf16 or fp32)
+};
+int32_t launch_edge_fwd(hipStream_t st, int H, bool bf16, const EdgeFwdArgs& a);
+
+// M[i,:] = alpha * sum_{e in row i} silu(z2[e,:]);  v_out = v_in + alpha * sum (wx . silu(z2[e,:])) rvec[e,:]
+int32_t launch_seg_fwd_vm(hipStream_t st, int H, bool bf16, int N, const int32_t* row_ptr, const void* z2_vm,
+                          const float* rvec, const float* wx, float alpha, const float* v_in, float* M,
+                          float* v_out);
+
+struct EdgeBwdArgs {
+  int64_t E;
+  const int32_t *dst, *col;
+  const float* d2;
+  const float* PQ;
+  const float* w1d;
+  const void* W2Tp;    // packed W2^T block
+  const void* z2_vm;   // saved by the forward kernel
+  const float* gM;     // [N, ldgM] gradient of the aggregated messages
+  int ldgM;
+  const float* cvec;   // [E] c_e = alpha * (g_v[dst[e]] . rvec[e])
+  const float* wx;     // [H]
+  float alpha;
+  void* gz2_pk;        // out: g_z2, operand-packed
+  float* gz1_vm;       // out: g_z1, v-major fp32
+  float* colpart;      // scratch: [splits][3][H] partial column sums (b2, wx, w1d)
+  float* g_b2;         // out [H]
+  float* g_wx;         // out [H]
+  float* g_w1d;        // out [H]
+};
+size_t edge_bwd_colpart_floats(int H);
+int32_t launch_edge_bwd(hipStream_t st, int H, bool bf16, const EdgeBwdArgs& a);
+
+// c[e] = alpha * (g_v[dst[e],:] . rvec[e,:])
+int32_t launch_edge_cvec(hipStream_t st, int64_t E, const int32_t* dst, const float* rvec, const float* g_v,
+                         float alpha, float* cvec);
+
+// gW2[k1][k2] = sum_e a1[e][k1] * g_z2[e][k2], both operands operand-packed; partial: scratch
+size_t wgrad_frag_partial_floats(int H);
+int32_t launch_wgrad_frag(hipStream_t st, int H, bool bf16, int64_t E, const void* a1_pk, const void* gz2_pk,
+                          float* partial, float* gW2);
+
+// out[i, 0..H) (row pitch ldo) = sum over t in ptr[i]:ptr[i+1] of X[perm ? perm[t] : t, :], X v-major fp32
+int32_t launch_segsum_vm(hipStream_t st, int H, int N, const int32_t* ptr, const int32_t* perm, const float* X_vm,
+                         float* out, int ldo, int tag);
+
+}  // namespace hgnn

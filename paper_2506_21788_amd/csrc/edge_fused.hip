@@ -1,0 +1,668 @@
+// Fused per-edge kernels (see edge_fused.h for the fragment-order layouts).
+//
+//   k_edge_fwd    gather P[dst]+Q[col]+d2*w1d -> SiLU -> (A tile in LDS) x W2 on the matrix cores -> z2
+//   k_seg_fwd_vm  destination-sorted segmented reduction of SiLU(z2) into M and the vector channel
+//   k_edge_bwd    g_z2 from z2 / g_M / g_v -> x W2^T -> recompute z1 -> g_z1, plus the three per-column
+//                 sums that are bias / vector gradients
+//   k_wgrad_frag  g_W2 = a1^T g_z2 streamed straight from memory into matrix-core operands
+//   k_segsum_vm   segmented sums of g_z1 per destination and (through the transpose plan) per source
+//
+// All element-wise work uses the accumulator mapping (lane <-> column, register <-> edge), so what one
+// kernel stores is what the next one loads, coalesced, without any transpose. Every sum has a fixed
+// order; there are no atomics.
+#include "devmath.h"
+#include "edge_fused.h"
+#include "gemm.h"
+
+namespace hgnn {
+
+template <int H, bool BF16>
+struct ECfg {
+  static constexpr int TM = 64;                       // edges per tile
+  static constexpr int NCB = H / 32;                  // 32-column blocks
+  static constexpr int WC = NCB < 4 ? NCB : 4;        // wavefronts over columns
+  static constexpr int WR = 4 / WC;                   // wavefronts over rows
+  static constexpr int RB = (TM / 32) / WR;           // 32-row blocks per wavefront
+  static constexpr int CB = NCB / WC;                 // 32-column blocks per wavefront
+  static constexpr int STRIDE = BF16 ? H + 8 : H + 4; // LDS row pitch (elements)
+  static constexpr size_t LDS_BYTES = (size_t)TM * STRIDE * (BF16 ? 2 : 4);
+};
+
+static int num_cus() {
+  static int n = 0;
+  if (n == 0) {
+    hipDeviceProp_t prop;
+    int dev = 0;
+    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
+      n = prop.multiProcessorCount;
+    if (n <= 0) n = 256;
+  }
+  return n;
+}
+
+__device__ __forceinline__ float bf_bits_to_f(unsigned short b) { return __uint_as_float(((unsigned)b) << 16); }
+
+// the 4 consecutive per-edge scalars e4..e4+3 (e4 is a multiple of 4); zeros beyond E
+__device__ __forceinline__ void load4(const int32_t* __restrict__ p, int64_t e4, int64_t E, int* o) {
+  if (e4 + 3 < E) {
+    const int4 t = *reinterpret_cast<const int4*>(p + e4);
+    o[0] = t.x; o[1] = t.y; o[2] = t.z; o[3] = t.w;
+  } else {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) o[i] = (e4 + i < E) ? p[e4 + i] : 0;
+  }
+}
+__device__ __forceinline__ void load4(const float* __restrict__ p, int64_t e4, int64_t E, float* o) {
+  if (e4 + 3 < E) {
+    const float4 t = *reinterpret_cast<const float4*>(p + e4);
+    o[0] = t.x; o[1] = t.y; o[2] = t.z; o[3] = t.w;
+  } else {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) o[i] = (e4 + i < E) ? p[e4 + i] : 0.f;
+  }
+}
+
+// store 16 accumulator-mapped values of one 32x32 block in operand-packed order
+template <bool BF16>
+__device__ __forceinline__ void store_packed(void* base, size_t blk, int lane, const float* vals) {
+  if (BF16) {
+    uint4* p = reinterpret_cast<uint4*>(base) + blk * 2 * 64 + lane;
+#pragma unroll
+    for (int vh = 0; vh < 2; ++vh) {
+      uint4 w;
+      w.x = pack_bf16x2(vals[vh * 8 + 0], vals[vh * 8 + 1]);
+      w.y = pack_bf16x2(vals[vh * 8 + 2], vals[vh * 8 + 3]);
+      w.z = pack_bf16x2(vals[vh * 8 + 4], vals[vh * 8 + 5]);
+      w.w = pack_bf16x2(vals[vh * 8 + 6], vals[vh * 8 + 7]);
+      p[vh * 64] = w;
+    }
+  } else {
+    float4* p = reinterpret_cast<float4*>(base) + blk * 4 * 64 + lane;
+#pragma unroll
+    for (int vq = 0; vq < 4; ++vq)
+      p[vq * 64] = make_float4(vals[vq * 4], vals[vq * 4 + 1], vals[vq * 4 + 2], vals[vq * 4 + 3]);
+  }
+}
+
+// A tile (LDS, row-major, padded) x packed B block -> accumulators; same tiling as the row-tile GEMM
+template <int H, bool BF16>
+__device__ __forceinline__ void tile_mma(const unsigned char* smem, const void* Bpacked, int wr, int wc, int lane,
+                                         f32x16_t (&acc)[ECfg<H, BF16>::RB][ECfg<H, BF16>::CB]) {
+  using C = ECfg<H, BF16>;
+  if (BF16) {
+    const bf16x8_t* __restrict__ Bp = reinterpret_cast<const bf16x8_t*>(Bpacked);
+    constexpr int NKB = H / 16;
+#pragma unroll 4
+    for (int kb = 0; kb < NKB; ++kb) {
+      bf16x8_t a[C::RB];
+#pragma unroll
+      for (int i = 0; i < C::RB; ++i) {
+        const int row = (wr * C::RB + i) * 32 + (lane & 31);
+        a[i] = *reinterpret_cast<const bf16x8_t*>(smem + ((size_t)row * C::STRIDE + kb * 16 + (lane >> 5) * 8) * 2);
+      }
+#pragma unroll
+      for (int j = 0; j < C::CB; ++j) {
+        const bf16x8_t b = Bp[((wc * C::CB + j) * NKB + kb) * 64 + lane];
+#pragma unroll
+        for (int i = 0; i < C::RB; ++i) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b, acc[i][j], 0, 0, 0);
+      }
+    }
+  } else {
+    const float4* __restrict__ Bp = reinterpret_cast<const float4*>(Bpacked);
+    constexpr int NKB = H / 8;
+#pragma unroll 4
+    for (int kb = 0; kb < NKB; ++kb) {
+      float4 a[C::RB];
+#pragma unroll
+      for (int i = 0; i < C::RB; ++i) {
+        const int row = (wr * C::RB + i) * 32 + (lane & 31);
+        a[i] = *reinterpret_cast<const float4*>(smem + ((size_t)row * C::STRIDE + kb * 8 + (lane >> 5) * 4) * 4);
+      }
+#pragma unroll
+      for (int j = 0; j < C::CB; ++j) {
+        const float4 b = Bp[((wc * C::CB + j) * NKB + kb) * 64 + lane];
+#pragma unroll
+        for (int i = 0; i < C::RB; ++i) {
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].x, b.x, acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].y, b.y, acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].z, b.z, acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].w, b.w, acc[i][j], 0, 0, 0);
+        }
+      }
+    }
+  }
+}
+
+template <bool BF16>
+__device__ __forceinline__ void lds_put(unsigned char* smem, int idx, float v) {
+  if (BF16) reinterpret_cast<unsigned short*>(smem)[idx] = (unsigned short)f2bf_bits(v);
+  else reinterpret_cast<float*>(smem)[idx] = v;
+}
+
+// ---------------------------------------------------------------------------------------------
+// forward
+// ---------------------------------------------------------------------------------------------
+template <int H, bool BF16>
+__global__ void __launch_bounds__(256) k_edge_fwd(EdgeFwdArgs p, int ntiles) {
+  using C = ECfg<H, BF16>;
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wr = wave / C::WC, wc = wave % C::WC;
+  const int g = lane >> 5, x = lane & 31;
+  const int64_t E = p.E;
+  float w1d[C::CB], b2[C::CB];
+#pragma unroll
+  for (int j = 0; j < C::CB; ++j) {
+    const int n = (wc * C::CB + j) * 32 + x;
+    w1d[j] = p.w1d[n];
+    b2[j] = p.b2[n];
+  }
+  for (int tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+    // ---- produce a1 for this wavefront's blocks: global (operand-packed) and LDS (row-major)
+#pragma unroll
+    for (int i = 0; i < C::RB; ++i) {
+      const int rblk = wr * C::RB + i;
+      const int64_t eb = (int64_t)tile * (C::TM / 32) + rblk;
+      if (eb * 32 >= E) continue;
+      int po[16], qo[16];
+      float dd[16];
+      unsigned ok = 0;
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) {
+        const int64_t e4 = eb * 32 + 8 * jj + 4 * g;
+        int di[4], ci[4];
+        load4(p.dst, e4, E, di);
+        load4(p.col, e4, E, ci);
+        load4(p.d2, e4, E, &dd[4 * jj]);
+#pragma unroll
+        for (int ii = 0; ii < 4; ++ii) {
+          po[4 * jj + ii] = di[ii] * 2 * H;
+          qo[4 * jj + ii] = ci[ii] * 2 * H + H;
+          ok |= (e4 + ii < E ? 1u : 0u) << (4 * jj + ii);
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < C::CB; ++j) {
+        const int cblk = wc * C::CB + j;
+        const int n = cblk * 32 + x;
+        float vals[16];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const float z = p.PQ[po[v] + n] + p.PQ[qo[v] + n] + dd[v] * w1d[j];
+          const float a = ((ok >> v) & 1u) ? silu_f(z) : 0.f;
+          vals[v] = a;
+          const int row = rblk * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
+          lds_put<BF16>(smem, row * C::STRIDE + n, a);
+        }
+        store_packed<BF16>(p.a1_pk, (size_t)eb * C::NCB + cblk, lane, vals);
+      }
+    }
+    __syncthreads();
+    f32x16_t acc[C::RB][C::CB];
+#pragma unroll
+    for (int i = 0; i < C::RB; ++i)
+#pragma unroll
+      for (int j = 0; j < C::CB; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+    tile_mma<H, BF16>(smem, p.W2p, wr, wc, lane, acc);
+    __syncthreads();
+    // ---- z2 = acc + b2, stored v-major
+#pragma unroll
+    for (int i = 0; i < C::RB; ++i) {
+      const int64_t eb = (int64_t)tile * (C::TM / 32) + wr * C::RB + i;
+      if (eb * 32 >= E) continue;
+#pragma unroll
+      for (int j = 0; j < C::CB; ++j) {
+        const size_t base = (((size_t)eb * C::NCB + (wc * C::CB + j)) * 16) * 64 + lane;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const float z = acc[i][j][v] + b2[j];
+          if (BF16) reinterpret_cast<unsigned short*>(p.z2_vm)[base + v * 64] = (unsigned short)f2bf_bits(z);
+          else reinterpret_cast<float*>(p.z2_vm)[base + v * 64] = z;
+        }
+      }
+    }
+  }
+}
+
+template <int H, bool BF16>
+static int32_t launch_edge_fwd_t(hipStream_t st, const EdgeFwdArgs& a) {
+  using C = ECfg<H, BF16>;
+  const int64_t ntiles = (a.E + C::TM - 1) / C::TM;
+  if (ntiles <= 0) return HGNN_OK;
+  static bool attr_set = false;
+  if (!attr_set) {
+    HGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_edge_fwd<H, BF16>),
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES));
+    attr_set = true;
+  }
+  int64_t grid = (int64_t)num_cus() * 4;
+  if (grid > ntiles) grid = ntiles;
+  ProfScope ps(PT_EDGE_FUSED_FWD, st);
+  k_edge_fwd<H, BF16><<<dim3((unsigned)grid), 256, C::LDS_BYTES, st>>>(a, (int)ntiles);
+  HGNN_LAUNCH_CHECK("k_edge_fwd");
+  return HGNN_OK;
+}
+
+int32_t launch_edge_fwd(hipStream_t st, int H, bool bf16, const EdgeFwdArgs& a) {
+  switch (H) {
+    case 64: return bf16 ? launch_edge_fwd_t<64, true>(st, a) : launch_edge_fwd_t<64, false>(st, a);
+    case 128: return bf16 ? launch_edge_fwd_t<128, true>(st, a) : launch_edge_fwd_t<128, false>(st, a);
+    case 256: return bf16 ? launch_edge_fwd_t<256, true>(st, a) : launch_edge_fwd_t<256, false>(st, a);
+  }
+  return set_error(HGNN_ERR_BAD_SHAPE, "H must be 64, 128 or 256 (got %d)", H);
+}
+
+// ---------------------------------------------------------------------------------------------
+// segmented reductions over v-major tensors: one wavefront per segment
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ float wave_sum64(float x) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o);
+  return x;
+}
+
+// element offset of (edge e, column block cb, lane-in-block x) in a v-major tensor
+template <int NCB>
+__device__ __forceinline__ size_t vm_index(size_t e, int cb, int x) {
+  const int r = (int)(e & 31);
+  const int v = 4 * (r >> 3) + (r & 3);
+  const int gg = (r >> 2) & 1;
+  return (((e >> 5) * NCB + cb) * 16 + v) * 64 + gg * 32 + x;
+}
+
+template <int H, bool BF16>
+__global__ void __launch_bounds__(256)
+k_seg_fwd_vm(int N, const int32_t* __restrict__ row_ptr, const void* __restrict__ z2_vm,
+             const float* __restrict__ rvec, const float* __restrict__ wx, float alpha,
+             const float* __restrict__ v_in, float* __restrict__ M, float* __restrict__ v_out) {
+  constexpr int NCB = H / 32;
+  constexpr int NC = NCB / 2;  // column blocks per lane half
+  const int i = __builtin_amdgcn_readfirstlane((int)(((size_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6));
+  const int lane = threadIdx.x & 63;
+  if (i >= N) return;
+  const int hp = lane >> 5, x = lane & 31;
+  const int e0 = row_ptr[i], e1 = row_ptr[i + 1];
+  float acc[NC], tx[NC], ty[NC], tz[NC];
+#pragma unroll
+  for (int c = 0; c < NC; ++c) acc[c] = tx[c] = ty[c] = tz[c] = 0.f;
+  for (int e = e0; e < e1; ++e) {
+    const float rx = rvec[3 * (size_t)e], ry = rvec[3 * (size_t)e + 1], rz = rvec[3 * (size_t)e + 2];
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+      const size_t idx = vm_index<NCB>((size_t)e, 2 * c + hp, x);
+      const float z = BF16 ? bf_bits_to_f(reinterpret_cast<const unsigned short*>(z2_vm)[idx])
+                           : reinterpret_cast<const float*>(z2_vm)[idx];
+      const float m = silu_f(z);
+      acc[c] += m;
+      tx[c] += m * rx;
+      ty[c] += m * ry;
+      tz[c] += m * rz;
+    }
+  }
+  float sx = 0.f, sy = 0.f, sz = 0.f;
+#pragma unroll
+  for (int c = 0; c < NC; ++c) {
+    const int n = (2 * c + hp) * 32 + x;
+    const float w = wx[n];
+    M[(size_t)i * H + n] = alpha * acc[c];
+    sx += w * tx[c];
+    sy += w * ty[c];
+    sz += w * tz[c];
+  }
+  sx = wave_sum64(sx);
+  sy = wave_sum64(sy);
+  sz = wave_sum64(sz);
+  if (lane == 0) {
+    v_out[3 * (size_t)i] = v_in[3 * (size_t)i] + alpha * sx;
+    v_out[3 * (size_t)i + 1] = v_in[3 * (size_t)i + 1] + alpha * sy;
+    v_out[3 * (size_t)i + 2] = v_in[3 * (size_t)i + 2] + alpha * sz;
+  }
+}
+
+int32_t launch_seg_fwd_vm(hipStream_t st, int H, bool bf16, int N, const int32_t* row_ptr, const void* z2_vm,
+                          const float* rvec, const float* wx, float alpha, const float* v_in, float* M,
+                          float* v_out) {
+  if (N <= 0) return HGNN_OK;
+  const unsigned grid = (unsigned)(((int64_t)N * 64 + 255) / 256);
+  ProfScope ps(PT_SEG_FWD, st);
+#define HGNN_SEGF(HH, BB) k_seg_fwd_vm<HH, BB><<<grid, 256, 0, st>>>(N, row_ptr, z2_vm, rvec, wx, alpha, v_in, M, v_out)
+  switch (H) {
+    case 64: if (bf16) HGNN_SEGF(64, true); else HGNN_SEGF(64, false); break;
+    case 128: if (bf16) HGNN_SEGF(128, true); else HGNN_SEGF(128, false); break;
+    case 256: if (bf16) HGNN_SEGF(256, true); else HGNN_SEGF(256, false); break;
+    default: return set_error(HGNN_ERR_BAD_SHAPE, "H must be 64, 128 or 256");
+  }
+#undef HGNN_SEGF
+  HGNN_LAUNCH_CHECK("k_seg_fwd_vm");
+  return HGNN_OK;
+}
+
+template <int H>
+__global__ void __launch_bounds__(256)
+k_segsum_vm(int N, const int32_t* __restrict__ ptr, const int32_t* __restrict__ perm, const float* __restrict__ X,
+            float* __restrict__ out, int ldo) {
+  constexpr int NCB = H / 32;
+  constexpr int NC = NCB / 2;
+  const int i = __builtin_amdgcn_readfirstlane((int)(((size_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6));
+  const int lane = threadIdx.x & 63;
+  if (i >= N) return;
+  const int hp = lane >> 5, x = lane & 31;
+  const int t0 = ptr[i], t1 = ptr[i + 1];
+  float acc[NC];
+#pragma unroll
+  for (int c = 0; c < NC; ++c) acc[c] = 0.f;
+  for (int t = t0; t < t1; ++t) {
+    const size_t e = perm ? (size_t)perm[t] : (size_t)t;
+#pragma unroll
+    for (int c = 0; c < NC; ++c) acc[c] += X[vm_index<NCB>(e, 2 * c + hp, x)];
+  }
+#pragma unroll
+  for (int c = 0; c < NC; ++c) out[(size_t)i * ldo + (2 * c + hp) * 32 + x] = acc[c];
+}
+
+int32_t launch_segsum_vm(hipStream_t st, int H, int N, const int32_t* ptr, const int32_t* perm, const float* X_vm,
+                         float* out, int ldo, int tag) {
+  if (N <= 0) return HGNN_OK;
+  const unsigned grid = (unsigned)(((int64_t)N * 64 + 255) / 256);
+  ProfScope ps(tag, st);
+  switch (H) {
+    case 64: k_segsum_vm<64><<<grid, 256, 0, st>>>(N, ptr, perm, X_vm, out, ldo); break;
+    case 128: k_segsum_vm<128><<<grid, 256, 0, st>>>(N, ptr, perm, X_vm, out, ldo); break;
+    case 256: k_segsum_vm<256><<<grid, 256, 0, st>>>(N, ptr, perm, X_vm, out, ldo); break;
+    default: return set_error(HGNN_ERR_BAD_SHAPE, "H must be 64, 128 or 256");
+  }
+  HGNN_LAUNCH_CHECK("k_segsum_vm");
+  return HGNN_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// backward
+// ---------------------------------------------------------------------------------------------
+__global__ void k_edge_cvec(int64_t E, const int32_t* __restrict__ dst, const float* __restrict__ rvec,
+                            const float* __restrict__ g_v, float alpha, float* __restrict__ cvec) {
+  const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= E) return;
+  const size_t i = (size_t)dst[e];
+  cvec[e] = alpha * (g_v[3 * i] * rvec[3 * e] + g_v[3 * i + 1] * rvec[3 * e + 1] + g_v[3 * i + 2] * rvec[3 * e + 2]);
+}
+
+int32_t launch_edge_cvec(hipStream_t st, int64_t E, const int32_t* dst, const float* rvec, const float* g_v,
+                         float alpha, float* cvec) {
+  if (E <= 0) return HGNN_OK;
+  ProfScope ps(PT_MISC, st);
+  k_edge_cvec<<<(unsigned)((E + 255) / 256), 256, 0, st>>>(E, dst, rvec, g_v, alpha, cvec);
+  HGNN_LAUNCH_CHECK("k_edge_cvec");
+  return HGNN_OK;
+}
+
+template <int H, bool BF16>
+__global__ void __launch_bounds__(256) k_edge_bwd(EdgeBwdArgs p, int ntiles) {
+  using C = ECfg<H, BF16>;
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wr = wave / C::WC, wc = wave % C::WC;
+  const int g = lane >> 5, x = lane & 31;
+  const int64_t E = p.E;
+  float w1d[C::CB], wxn[C::CB], sb2[C::CB], swx[C::CB], sw1[C::CB];
+#pragma unroll
+  for (int j = 0; j < C::CB; ++j) {
+    const int n = (wc * C::CB + j) * 32 + x;
+    w1d[j] = p.w1d[n];
+    wxn[j] = p.wx[n];
+    sb2[j] = swx[j] = sw1[j] = 0.f;
+  }
+  for (int tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+    // ---- g_z2 = (alpha*g_M[dst] + c*wx) * silu'(z2): operand-packed to memory, row-major to LDS
+#pragma unroll
+    for (int i = 0; i < C::RB; ++i) {
+      const int rblk = wr * C::RB + i;
+      const int64_t eb = (int64_t)tile * (C::TM / 32) + rblk;
+      if (eb * 32 >= E) continue;
+      int mo[16];
+      float cc[16];
+      unsigned ok = 0;
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) {
+        const int64_t e4 = eb * 32 + 8 * jj + 4 * g;
+        int di[4];
+        load4(p.dst, e4, E, di);
+        load4(p.cvec, e4, E, &cc[4 * jj]);
+#pragma unroll
+        for (int ii = 0; ii < 4; ++ii) {
+          mo[4 * jj + ii] = di[ii] * p.ldgM;
+          ok |= (e4 + ii < E ? 1u : 0u) << (4 * jj + ii);
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < C::CB; ++j) {
+        const int cblk = wc * C::CB + j;
+        const int n = cblk * 32 + x;
+        const size_t zbase = (((size_t)eb * C::NCB + cblk) * 16) * 64 + lane;
+        float vals[16];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const float z = BF16 ? bf_bits_to_f(reinterpret_cast<const unsigned short*>(p.z2_vm)[zbase + v * 64])
+                               : reinterpret_cast<const float*>(p.z2_vm)[zbase + v * 64];
+          float m, dm;
+          silu_both(z, m, dm);
+          float gz = (p.alpha * p.gM[mo[v] + n] + cc[v] * wxn[j]) * dm;
+          if (!((ok >> v) & 1u)) { gz = 0.f; m = 0.f; }
+          vals[v] = gz;
+          sb2[j] += gz;
+          swx[j] += cc[v] * m;
+          const int row = rblk * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
+          lds_put<BF16>(smem, row * C::STRIDE + n, gz);
+        }
+        store_packed<BF16>(p.gz2_pk, (size_t)eb * C::NCB + cblk, lane, vals);
+      }
+    }
+    __syncthreads();
+    f32x16_t acc[C::RB][C::CB];
+#pragma unroll
+    for (int i = 0; i < C::RB; ++i)
+#pragma unroll
+      for (int j = 0; j < C::CB; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+    tile_mma<H, BF16>(smem, p.W2Tp, wr, wc, lane, acc);
+    __syncthreads();
+    // ---- g_z1 = g_a1 * silu'(z1), z1 recomputed from the projected node features
+#pragma unroll
+    for (int i = 0; i < C::RB; ++i) {
+      const int64_t eb = (int64_t)tile * (C::TM / 32) + wr * C::RB + i;
+      if (eb * 32 >= E) continue;
+      int po[16], qo[16];
+      float dd[16];
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) {
+        const int64_t e4 = eb * 32 + 8 * jj + 4 * g;
+        int di[4], ci[4];
+        load4(p.dst, e4, E, di);
+        load4(p.col, e4, E, ci);
+        load4(p.d2, e4, E, &dd[4 * jj]);
+#pragma unroll
+        for (int ii = 0; ii < 4; ++ii) {
+          po[4 * jj + ii] = di[ii] * 2 * H;
+          qo[4 * jj + ii] = ci[ii] * 2 * H + H;
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < C::CB; ++j) {
+        const int cblk = wc * C::CB + j;
+        const int n = cblk * 32 + x;
+        const size_t base = (((size_t)eb * C::NCB + cblk) * 16) * 64 + lane;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const float z1 = p.PQ[po[v] + n] + p.PQ[qo[v] + n] + dd[v] * w1d[j];
+          const float gz1 = acc[i][j][v] * dsilu_f(z1);   // rows beyond E have acc == 0
+          p.gz1_vm[base + v * 64] = gz1;
+          sw1[j] += dd[v] * gz1;
+        }
+      }
+    }
+  }
+  // ---- per-column partial sums of this wavefront: combine the two lane halves, one writer per column
+#pragma unroll
+  for (int j = 0; j < C::CB; ++j) {
+    const float a = sb2[j] + __shfl_xor(sb2[j], 32);
+    const float b = swx[j] + __shfl_xor(swx[j], 32);
+    const float c = sw1[j] + __shfl_xor(sw1[j], 32);
+    if (g == 0) {
+      const int n = (wc * C::CB + j) * 32 + x;
+      float* o = p.colpart + ((size_t)(blockIdx.x * C::WR + wr) * 3) * H + n;
+      o[0] = a;
+      o[H] = b;
+      o[2 * H] = c;
+    }
+  }
+}
+
+constexpr int EDGE_BWD_MAX_GRID = 2048;
+size_t edge_bwd_colpart_floats(int H) { return (size_t)EDGE_BWD_MAX_GRID * 2 * 3 * H; }
+
+template <int H, bool BF16>
+static int32_t launch_edge_bwd_t(hipStream_t st, const EdgeBwdArgs& a) {
+  using C = ECfg<H, BF16>;
+  const int64_t ntiles = (a.E + C::TM - 1) / C::TM;
+  static bool attr_set = false;
+  if (!attr_set) {
+    HGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_edge_bwd<H, BF16>),
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES));
+    attr_set = true;
+  }
+  int64_t grid = (int64_t)num_cus() * 4;
+  if (grid > EDGE_BWD_MAX_GRID) grid = EDGE_BWD_MAX_GRID;
+  if (grid > ntiles) grid = ntiles;
+  if (grid < 1) grid = 1;  // E == 0: one block writes zero partials
+  {
+    ProfScope ps(PT_EDGE_FUSED_BWD, st);
+    k_edge_bwd<H, BF16><<<dim3((unsigned)grid), 256, C::LDS_BYTES, st>>>(a, (int)ntiles);
+    HGNN_LAUNCH_CHECK("k_edge_bwd");
+  }
+  float* dest[4] = {a.g_b2, a.g_wx, a.g_w1d, nullptr};
+  return launch_reduce_partials(st, a.colpart, (int)grid * C::WR, 3, H, dest, 1, 0);
+}
+
+int32_t launch_edge_bwd(hipStream_t st, int H, bool bf16, const EdgeBwdArgs& a) {
+  switch (H) {
+    case 64: return bf16 ? launch_edge_bwd_t<64, true>(st, a) : launch_edge_bwd_t<64, false>(st, a);
+    case 128: return bf16 ? launch_edge_bwd_t<128, true>(st, a) : launch_edge_bwd_t<128, false>(st, a);
+    case 256: return bf16 ? launch_edge_bwd_t<256, true>(st, a) : launch_edge_bwd_t<256, false>(st, a);
+  }
+  return set_error(HGNN_ERR_BAD_SHAPE, "H must be 64, 128 or 256 (got %d)", H);
+}
+
+// ---------------------------------------------------------------------------------------------
+// weight gradient of W2: operands streamed in operand-packed order, contraction over edges
+// ---------------------------------------------------------------------------------------------
+template <int H, bool BF16>
+__global__ void __launch_bounds__(256)
+k_wgrad_frag(int64_t nblk32, int blocks_per_wg, const void* __restrict__ a1_pk, const void* __restrict__ gz2_pk,
+             float* __restrict__ partial) {
+  constexpr int NCB = H / 32;
+  constexpr int NBW = NCB / 2;  // 32-blocks per wavefront along each output dimension
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wa = wave >> 1, wb = wave & 1;
+  f32x16_t acc[NBW][NBW];
+#pragma unroll
+  for (int i = 0; i < NBW; ++i)
+#pragma unroll
+    for (int j = 0; j < NBW; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+  int64_t eb0 = (int64_t)blockIdx.x * blocks_per_wg;
+  int64_t eb1 = eb0 + blocks_per_wg;
+  if (eb1 > nblk32) eb1 = nblk32;
+  if (BF16) {
+    const bf16x8_t* __restrict__ A = reinterpret_cast<const bf16x8_t*>(a1_pk);
+    const bf16x8_t* __restrict__ B = reinterpret_cast<const bf16x8_t*>(gz2_pk);
+    for (int64_t eb = eb0; eb < eb1; ++eb) {
+#pragma unroll
+      for (int vh = 0; vh < 2; ++vh) {
+        bf16x8_t a[NBW], b[NBW];
+#pragma unroll
+        for (int i = 0; i < NBW; ++i) {
+          a[i] = A[(((size_t)eb * NCB + wa * NBW + i) * 2 + vh) * 64 + lane];
+          b[i] = B[(((size_t)eb * NCB + wb * NBW + i) * 2 + vh) * 64 + lane];
+        }
+#pragma unroll
+        for (int i = 0; i < NBW; ++i)
+#pragma unroll
+          for (int j = 0; j < NBW; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+      }
+    }
+  } else {
+    const float4* __restrict__ A = reinterpret_cast<const float4*>(a1_pk);
+    const float4* __restrict__ B = reinterpret_cast<const float4*>(gz2_pk);
+    for (int64_t eb = eb0; eb < eb1; ++eb) {
+#pragma unroll
+      for (int vq = 0; vq < 4; ++vq) {
+        float4 a[NBW], b[NBW];
+#pragma unroll
+        for (int i = 0; i < NBW; ++i) {
+          a[i] = A[(((size_t)eb * NCB + wa * NBW + i) * 4 + vq) * 64 + lane];
+          b[i] = B[(((size_t)eb * NCB + wb * NBW + i) * 4 + vq) * 64 + lane];
+        }
+#pragma unroll
+        for (int i = 0; i < NBW; ++i)
+#pragma unroll
+          for (int j = 0; j < NBW; ++j) {
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].x, b[j].x, acc[i][j], 0, 0, 0);
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].y, b[j].y, acc[i][j], 0, 0, 0);
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].z, b[j].z, acc[i][j], 0, 0, 0);
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].w, b[j].w, acc[i][j], 0, 0, 0);
+          }
+      }
+    }
+  }
+  float* out = partial + (size_t)blockIdx.x * H * H;
+#pragma unroll
+  for (int i = 0; i < NBW; ++i)
+#pragma unroll
+    for (int j = 0; j < NBW; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int k1 = (wa * NBW + i) * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+        const int k2 = (wb * NBW + j) * 32 + (lane & 31);
+        out[k1 * H + k2] = acc[i][j][v];
+      }
+}
+
+constexpr int WGRAD_FRAG_MAX_GRID = 512;
+size_t wgrad_frag_partial_floats(int H) { return (size_t)WGRAD_FRAG_MAX_GRID * H * H; }
+
+template <int H, bool BF16>
+static int32_t launch_wgrad_frag_t(hipStream_t st, int64_t E, const void* a1_pk, const void* gz2_pk, float* partial,
+                                   float* gW2) {
+  const int64_t nblk32 = (E + 31) / 32;
+  int64_t grid = (int64_t)num_cus() * (H == 256 ? 1 : 2);
+  if (grid > WGRAD_FRAG_MAX_GRID) grid = WGRAD_FRAG_MAX_GRID;
+  if (grid > nblk32) grid = nblk32;
+  if (grid < 1) grid = 1;
+  const int64_t per = nblk32 > 0 ? (nblk32 + grid - 1) / grid : 0;
+  {
+    ProfScope ps(PT_WGRAD_EDGE, st);
+    k_wgrad_frag<H, BF16><<<dim3((unsigned)grid), 256, 0, st>>>(nblk32, (int)per, a1_pk, gz2_pk, partial);
+    HGNN_LAUNCH_CHECK("k_wgrad_frag");
+  }
+  float* dest[4] = {gW2, nullptr, nullptr, nullptr};
+  return launch_reduce_partials(st, partial, (int)grid, 1, (long)H * H, dest, 1, 0);
+}
+
+int32_t launch_wgrad_frag(hipStream_t st, int H, bool bf16, int64_t E, const void* a1_pk, const void* gz2_pk,
+                          float* partial, float* gW2) {
+  switch (H) {
+    case 64: return bf16 ? launch_wgrad_frag_t<64, true>(st, E, a1_pk, gz2_pk, partial, gW2)
+                         : launch_wgrad_frag_t<64, false>(st, E, a1_pk, gz2_pk, partial, gW2);
+    case 128: return bf16 ? launch_wgrad_frag_t<128, true>(st, E, a1_pk, gz2_pk, partial, gW2)
+                          : launch_wgrad_frag_t<128, false>(st, E, a1_pk, gz2_pk, partial, gW2);
+    case 256: return bf16 ? launch_wgrad_frag_t<256, true>(st, E, a1_pk, gz2_pk, partial, gW2)
+                          : launch_wgrad_frag_t<256, false>(st, E, a1_pk, gz2_pk, partial, gW2);
+  }
+  return set_error(HGNN_ERR_BAD_SHAPE, "H must be 64, 128 or 256 (got %d)", H);
+}
+
+}  // namespace hgnn

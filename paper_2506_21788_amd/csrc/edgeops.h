@@ -3,6 +3,7 @@
 #pragma once
 
 #include "common.h"
+#include "prof.h"
 
 namespace hgnn {
 
@@ -23,7 +24,7 @@ int32_t launch_edge_gz2(hipStream_t st, int H, int64_t E, const int32_t* dst, co
 
 // out[i,:] = sum over t in ptr[i]:ptr[i+1] of X[perm ? perm[t] : t, :]
 int32_t launch_segsum(hipStream_t st, int H, int N, const int32_t* ptr, const int32_t* perm, const float* X,
-                      float* out, int ldo);
+                      float* out, int ldo, int tag);
 
 int32_t launch_copy_f32(hipStream_t st, const float* src, float* dst, int64_t n);
 int32_t launch_fill_f32(hipStream_t st, float* dst, int64_t n, float v);

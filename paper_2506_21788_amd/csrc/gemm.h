@@ -4,6 +4,7 @@
 #pragma once
 
 #include "common.h"
+#include "prof.h"
 
 namespace hgnn {
 
@@ -52,6 +53,7 @@ struct GemmArgs {
   float* C = nullptr;
   int ldc = 0;
   int ncb = 1;
+  int tag = PT_GEMM_NODE;  // timing class
 };
 int32_t launch_gemm(hipStream_t st, int H, bool bf16, const GemmArgs& a);
 
@@ -72,6 +74,7 @@ struct WgradArgs {
   float* dest[4] = {nullptr, nullptr, nullptr, nullptr};  // block ia*nB+ib -> H*H floats, row-major
   long grp_dest_stride = 0;
   float* partial = nullptr;  // scratch, wgrad_partial_floats()
+  int tag = PT_WGRAD_NODE;
 };
 int wgrad_splits(int64_t M);
 size_t wgrad_partial_floats(int H, int64_t M, int nblocks, int S);
@@ -94,5 +97,10 @@ struct ColsumArgs {
 };
 size_t colsum_partial_floats(int H, int64_t M, int S);
 int32_t launch_colsum(hipStream_t st, int H, const ColsumArgs& a);
+
+// dest[blk][i] (+ grp*grp_dest_stride) = sum over s < nsplit of partial[((grp*nsplit + s)*nblk + blk)*blk_elems + i],
+// summed in ascending s
+int32_t launch_reduce_partials(hipStream_t st, const float* partial, int nsplit, int nblk, long blk_elems,
+                               float* const dest[4], int groups, long grp_dest_stride);
 
 }  // namespace hgnn

@@ -50,6 +50,7 @@ __global__ void k_pack(PackArgs a, int H, long src_grp_stride, long dst_grp_stri
 int32_t launch_pack(hipStream_t st, int H, bool bf16, const PackArgs& a, int groups, long src_grp_stride,
                     long dst_grp_stride_elems) {
   if (a.nblocks <= 0 || groups <= 0) return HGNN_OK;
+  ProfScope ps(PT_PACK, st);
   dim3 grid((H * H + 255) / 256, a.nblocks, groups);
   if (bf16) k_pack<true><<<grid, 256, 0, st>>>(a, H, src_grp_stride, dst_grp_stride_elems);
   else k_pack<false><<<grid, 256, 0, st>>>(a, H, src_grp_stride, dst_grp_stride_elems);
@@ -229,6 +230,7 @@ static int32_t launch_gemm_t(hipStream_t st, const GemmArgs& a) {
                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES));
     attr_set = true;
   }
+  ProfScope ps(a.tag, st);
   k_gemm<H, BF16><<<dim3(tiles, a.ncb), 256, C::LDS_BYTES, st>>>(a);
   HGNN_LAUNCH_CHECK("k_gemm");
   return HGNN_OK;
@@ -266,6 +268,20 @@ __global__ void k_reduce_partials(ReduceArgs a) {
   float s = 0.f;
   for (int k = 0; k < a.nsplit; ++k) s += p[k * step];
   a.dest[blk][grp * a.grp_dest_stride + i] = s;
+}
+
+int32_t launch_reduce_partials(hipStream_t st, const float* partial, int nsplit, int nblk, long blk_elems,
+                               float* const dest[4], int groups, long grp_dest_stride) {
+  ReduceArgs r;
+  r.partial = partial;
+  r.nsplit = nsplit;
+  r.nblk = nblk;
+  r.blk_elems = blk_elems;
+  for (int i = 0; i < 4; ++i) r.dest[i] = dest[i];
+  r.grp_dest_stride = grp_dest_stride;
+  k_reduce_partials<<<dim3((unsigned)((blk_elems + 255) / 256), nblk, groups), 256, 0, st>>>(r);
+  HGNN_LAUNCH_CHECK("k_reduce_partials");
+  return HGNN_OK;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -407,6 +423,7 @@ static int32_t launch_wgrad_t(hipStream_t st, const WgradArgs& a) {
   if (rps < WG_RC) rps = WG_RC;
   const int nblk = a.nA * a.nB;
   const int groups = a.grp_ptr ? a.S : 1;
+  ProfScope ps(a.tag, st);
   k_wgrad<H, BF16><<<dim3(nsplit, nblk * C::TILES * C::TILES, groups), 256, 0, st>>>(a, nsplit, (int)rps);
   HGNN_LAUNCH_CHECK("k_wgrad");
   ReduceArgs r;
@@ -477,6 +494,7 @@ int32_t launch_colsum(hipStream_t st, int H, const ColsumArgs& a) {
   int64_t rps = (a.M + nsplit - 1) / nsplit;
   if (rps < 1) rps = 1;
   const int groups = a.grp_ptr ? a.S : 1;
+  ProfScope ps(PT_COLSUM, st);
   k_colsum<<<dim3(nsplit, groups), 256, 0, st>>>(a, H, nsplit, (int)rps);
   HGNN_LAUNCH_CHECK("k_colsum");
   ReduceArgs r;

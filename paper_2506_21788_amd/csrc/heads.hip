@@ -339,6 +339,7 @@ extern "C" int32_t hgnn_embed_fwd(void* stream, int32_t N, int32_t H, const int3
   HGNN_REQUIRE(N >= 0 && valid_H(H), HGNN_ERR_BAD_SHAPE, "embed_fwd: bad N or H");
   if (N == 0) return HGNN_OK;
   HGNN_REQUIRE(Z && emb && h, HGNN_ERR_NULLPTR, "embed_fwd: null pointer");
+  ProfScope ps(PT_EMBED, st);
   k_embed_fwd<<<nb64((int64_t)N * (H / 4), 256), 256, 0, st>>>(N, H, Z, emb, h);
   HGNN_LAUNCH_CHECK("k_embed_fwd");
   return HGNN_OK;
@@ -348,6 +349,7 @@ extern "C" int32_t hgnn_embed_bwd(void* stream, int32_t N, int32_t H, const int3
   hipStream_t st = static_cast<hipStream_t>(stream);
   HGNN_REQUIRE(N >= 0 && valid_H(H), HGNN_ERR_BAD_SHAPE, "embed_bwd: bad N or H");
   HGNN_REQUIRE(g_emb && (N == 0 || (Z && g_h)), HGNN_ERR_NULLPTR, "embed_bwd: null pointer");
+  ProfScope ps(PT_EMBED, st);
   k_embed_bwd<<<HGNN_ZMAX + 1, 256, 0, st>>>(N, H, Z, g_h, g_emb);
   HGNN_LAUNCH_CHECK("k_embed_bwd");
   return HGNN_OK;
@@ -360,6 +362,7 @@ extern "C" int32_t hgnn_pool_by_graph_fwd(void* stream, int32_t N, int32_t G, in
   HGNN_REQUIRE(mode == HGNN_POOL_SUM || mode == HGNN_POOL_MEAN, HGNN_ERR_BAD_SHAPE, "pool_fwd: unknown mode");
   if (G == 0) return HGNN_OK;
   HGNN_REQUIRE(graph_off && p && (h || N == 0), HGNN_ERR_NULLPTR, "pool_fwd: null pointer");
+  ProfScope ps(PT_POOL, st);
   k_pool_fwd<<<G, 1024, 0, st>>>(H, mode, graph_off, h, p);
   HGNN_LAUNCH_CHECK("k_pool_fwd");
   return HGNN_OK;
@@ -372,6 +375,7 @@ extern "C" int32_t hgnn_pool_by_graph_bwd(void* stream, int32_t N, int32_t G, in
   HGNN_REQUIRE(mode == HGNN_POOL_SUM || mode == HGNN_POOL_MEAN, HGNN_ERR_BAD_SHAPE, "pool_bwd: unknown mode");
   if (N == 0) return HGNN_OK;
   HGNN_REQUIRE(G > 0 && graph_off && g_p && g_h, HGNN_ERR_NULLPTR, "pool_bwd: null pointer");
+  ProfScope ps(PT_POOL, st);
   k_pool_bwd<<<nb64((int64_t)N * (H / 4), 256), 256, 0, st>>>(N, G, H, mode, graph_off, g_p, g_h, accumulate);
   HGNN_LAUNCH_CHECK("k_pool_bwd");
   return HGNN_OK;
@@ -456,6 +460,7 @@ extern "C" int32_t hgnn_multihead_decode_fwd(void* stream, int32_t N, int32_t G,
     g.C = s.zf; g.ldc = Hh;
     HGNN_TRY(launch_gemm(st, H, bf16, g));
   }
+  ProfScope ps(PT_HEAD_OUT, st);
   k_head_out_fwd<<<nb64((int64_t)(G + N) * 64, 256), 256, 0, st>>>(N, G, Hh, s.ze, s.zf, Whead, o, pv.graph_src,
                                                                     pv.atom_graph, v, energy, force, s.q);
   HGNN_LAUNCH_CHECK("k_head_out_fwd");
@@ -492,9 +497,12 @@ extern "C" int32_t hgnn_multihead_decode_bwd(void* stream, int32_t N, int32_t G,
   pk.d[1] = {o.Wf1, 1, Hh};
   HGNN_TRY(launch_pack(st, H, bf16, pk, S, o.per, 2 * HH));
 
+  {
+  ProfScope ps(PT_HEAD_OUT, st);
   k_head_out_bwd<<<nb64((int64_t)(G + N) * 64, 256), 256, 0, st>>>(N, G, Hh, s.ze, s.zf, Whead, o, pv.graph_src,
                                                                     pv.atom_graph, v, s.q, g_energy, g_force, w.g_ze,
                                                                     w.g_zf, w.gq, g_v);
+  }
   HGNN_LAUNCH_CHECK("k_head_out_bwd");
 
   // ---- energy branch (rows = graphs) and force branch (rows = atoms), same five steps each

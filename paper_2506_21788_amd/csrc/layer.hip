@@ -6,6 +6,7 @@
 // gathers and adds two rows. The per-edge matrix work is then the single H x H product with W2.
 // The reverse pass mirrors this: the gradient with respect to z1 is reduced per destination (g_P)
 // and per source (g_Q, through the source-sorted plan) and the W1 products run per atom again.
+#include "edge_fused.h"
 #include "edgeops.h"
 #include "gemm.h"
 
@@ -29,18 +30,21 @@ struct LayerOff {  // element offsets into the flat weight buffer
 };
 
 struct LayerSaved {
-  float* PQ;  // [N,2H]  P = h W1a + b1 | Q = h W1b
-  float* z2;  // [E,H]
-  float* M;   // [N,H]
-  float* z3;  // [N,H]
+  float* PQ;    // [N,2H]  P = h W1a + b1 | Q = h W1b
+  void* z2_vm;  // [E32,H] z2, v-major fragment order (bf16 or fp32)
+  void* a1_pk;  // [E32,H] silu(z1), operand-packed fragment order (bf16 or fp32)
+  float* M;     // [N,H]
+  float* z3;    // [N,H]
   size_t bytes;
 };
 
-static LayerSaved carve_saved(void* p, int N, int64_t E, int H) {
+static LayerSaved carve_saved(void* p, int N, int64_t E, int H, bool bf16) {
   Carver c(p);
   LayerSaved s;
+  const size_t eb = frag_rows(E) * H * (bf16 ? 2 : 4);
   s.PQ = c.take<float>((size_t)N * 2 * H);
-  s.z2 = c.take<float>((size_t)E * H);
+  s.z2_vm = c.take<char>(eb);
+  s.a1_pk = c.take<char>(eb);
   s.M = c.take<float>((size_t)N * H);
   s.z3 = c.take<float>((size_t)N * H);
   s.bytes = c.used();
@@ -49,9 +53,8 @@ static LayerSaved carve_saved(void* p, int N, int64_t E, int H) {
 
 struct LayerWs {
   void* packed;    // 6 blocks
-  float* a1;       // [E,H]
-  float* s1;       // [E,H]  silu'(z1), overwritten in place by g_z1
-  float* g_z2;     // [E,H]
+  void* gz2_pk;    // [E32,H] operand-packed
+  float* gz1_vm;   // [E32,H] v-major fp32
   float* cvec;     // [E]
   float* g_z3;     // [N,H]
   float* g_hM;     // [N,2H]
@@ -64,17 +67,16 @@ static LayerWs carve_ws(void* p, int N, int64_t E, int H, bool bf16) {
   Carver c(p);
   LayerWs w;
   w.packed = c.take<char>(6 * packed_block_bytes(H, bf16));
-  w.a1 = c.take<float>((size_t)E * H);
-  w.s1 = c.take<float>((size_t)E * H);
-  w.g_z2 = c.take<float>((size_t)E * H);
-  w.cvec = c.take<float>((size_t)E + 1);
+  w.gz2_pk = c.take<char>(frag_rows(E) * H * (bf16 ? 2 : 4));
+  w.gz1_vm = c.take<float>(frag_rows(E) * H);
+  w.cvec = c.take<float>((size_t)E + 4);
   w.g_z3 = c.take<float>((size_t)N * H);
   w.g_hM = c.take<float>((size_t)N * 2 * H);
   w.g_PQ = c.take<float>((size_t)N * 2 * H);
-  const int64_t mx = E > N ? E : N;
-  size_t pf = wgrad_partial_floats(H, mx, 2, 1);
-  size_t cf = colsum_partial_floats(H, mx, 1);
-  w.partial = c.take<float>(pf > cf ? pf : cf);
+  size_t pf = wgrad_partial_floats(H, N, 2, 1);
+  const size_t cands[3] = {colsum_partial_floats(H, N, 1), wgrad_frag_partial_floats(H), edge_bwd_colpart_floats(H)};
+  for (size_t x : cands) pf = x > pf ? x : pf;
+  w.partial = c.take<float>(pf);
   w.bytes = c.used();
   return w;
 }
@@ -96,7 +98,7 @@ extern "C" int32_t hgnn_mp_layer_workspace_bytes(int32_t N, int64_t E, int32_t H
   HGNN_TRY(check_layer_args(N, E, H, dtype));
   HGNN_REQUIRE(ws_bytes_host && saved_bytes_host, HGNN_ERR_NULLPTR, "null size pointer");
   *ws_bytes_host = carve_ws(nullptr, N, E, H, dtype == HGNN_BF16).bytes;
-  *saved_bytes_host = carve_saved(nullptr, N, E, H).bytes;
+  *saved_bytes_host = carve_saved(nullptr, N, E, H, dtype == HGNN_BF16).bytes;
   return HGNN_OK;
 }
 
@@ -115,7 +117,7 @@ extern "C" int32_t hgnn_mp_layer_fwd(void* stream, int32_t N, int64_t E, int32_t
   HGNN_REQUIRE(h_out != h_in, HGNN_ERR_BAD_SHAPE, "h_out may not alias h_in");
   const bool bf16 = dtype == HGNN_BF16;
   LayerWs w = carve_ws(ws, N, E, H, bf16);
-  LayerSaved s = carve_saved(saved, N, E, H);
+  LayerSaved s = carve_saved(saved, N, E, H, bf16);
   HGNN_REQUIRE(ws_bytes >= w.bytes, HGNN_ERR_WORKSPACE_TOO_SMALL, "mp_layer workspace: need %zu bytes, got %zu", w.bytes, ws_bytes);
   HGNN_REQUIRE(saved_bytes >= s.bytes, HGNN_ERR_WORKSPACE_TOO_SMALL, "mp_layer saved buffer: need %zu bytes, got %zu", s.bytes, saved_bytes);
   const LayerOff o(H);
@@ -143,17 +145,16 @@ extern "C" int32_t hgnn_mp_layer_fwd(void* stream, int32_t N, int64_t E, int32_t
     g.C = s.PQ; g.ldc = 2 * H;
     HGNN_TRY(launch_gemm(st, H, bf16, g));
   }
-  if (E > 0) {
-    HGNN_TRY(launch_edge_pre(st, H, E, dst, col, d2, s.PQ, W + o.W1 + 2 * HH, w.a1, nullptr));
-    GemmArgs g;
-    g.A[0] = w.a1; g.lda[0] = H;
-    g.B = w.packed; g.blk[0][0] = 2;
-    g.M = (int)E;
-    g.bias = W + o.b2; g.bias_cb_mask = 1;
-    g.C = s.z2; g.ldc = H;
-    HGNN_TRY(launch_gemm(st, H, bf16, g));
+  {  // per edge: a1 = silu(P[dst] + Q[col] + d2*w1d), z2 = a1 W2 + b2   (one fused kernel)
+    EdgeFwdArgs e;
+    e.E = E; e.dst = dst; e.col = col; e.d2 = d2;
+    e.PQ = s.PQ; e.w1d = W + o.W1 + 2 * HH;
+    e.W2p = static_cast<const char*>(w.packed) + 2 * packed_block_bytes(H, bf16);
+    e.b2 = W + o.b2;
+    e.a1_pk = s.a1_pk; e.z2_vm = s.z2_vm;
+    HGNN_TRY(launch_edge_fwd(st, H, bf16, e));
   }
-  HGNN_TRY(launch_seg_fwd(st, H, N, row_ptr, s.z2, rvec, W + o.wx, alpha, v_in, s.M, v_out));
+  HGNN_TRY(launch_seg_fwd_vm(st, H, bf16, N, row_ptr, s.z2_vm, rvec, W + o.wx, alpha, v_in, s.M, v_out));
   {  // z3 = [h ; M] W3 + b3
     GemmArgs g;
     g.A[0] = h_in; g.lda[0] = H; g.A[1] = s.M; g.lda[1] = H; g.nkc = 2;
@@ -192,7 +193,7 @@ extern "C" int32_t hgnn_mp_layer_bwd(void* stream, int32_t N, int64_t E, int32_t
   if (N == 0) return launch_fill_f32(st, gW, LayerOff(H).total, 0.f);
   const bool bf16 = dtype == HGNN_BF16;
   LayerWs w = carve_ws(ws, N, E, H, bf16);
-  LayerSaved s = carve_saved(const_cast<void*>(saved), N, E, H);
+  LayerSaved s = carve_saved(const_cast<void*>(saved), N, E, H, bf16);
   HGNN_REQUIRE(ws_bytes >= w.bytes, HGNN_ERR_WORKSPACE_TOO_SMALL, "mp_layer workspace: need %zu bytes, got %zu", w.bytes, ws_bytes);
   HGNN_REQUIRE(saved_bytes >= s.bytes, HGNN_ERR_WORKSPACE_TOO_SMALL, "mp_layer saved buffer: need %zu bytes, got %zu", s.bytes, saved_bytes);
   const LayerOff o(H);
@@ -253,42 +254,25 @@ extern "C" int32_t hgnn_mp_layer_bwd(void* stream, int32_t N, int64_t E, int32_t
     c.X = w.g_z3; c.ldx = H; c.M = N; c.dest = gW + o.b3; c.partial = w.partial;
     HGNN_TRY(launch_colsum(st, H, c));
   }
-  // edge part
-  HGNN_TRY(launch_edge_gz2(st, H, E, dst, rvec, s.z2, w.g_hM + H, 2 * H, g_v_out, W + o.wx, alpha, w.g_z2, w.cvec));
+  // edge part: c_e, then g_z2 -> (x W2^T) -> g_z1 with the per-column sums, then g_W2, then the two segment sums
+  HGNN_TRY(launch_edge_cvec(st, E, dst, rvec, g_v_out, alpha, w.cvec));
   {
-    ColsumArgs c;  // g_wx = sum_e c_e * m_e
-    c.X = s.z2; c.ldx = H; c.f_silu = 1; c.w = w.cvec; c.M = E; c.dest = gW + o.wx; c.partial = w.partial;
-    HGNN_TRY(launch_colsum(st, H, c));
-    ColsumArgs c2;  // gb2
-    c2.X = w.g_z2; c2.ldx = H; c2.M = E; c2.dest = gW + o.b2; c2.partial = w.partial;
-    HGNN_TRY(launch_colsum(st, H, c2));
+    EdgeBwdArgs e;
+    e.E = E; e.dst = dst; e.col = col; e.d2 = d2;
+    e.PQ = s.PQ; e.w1d = W + o.W1 + 2 * HH;
+    e.W2Tp = static_cast<const char*>(w.packed) + 3 * packed_block_bytes(H, bf16);
+    e.z2_vm = s.z2_vm;
+    e.gM = w.g_hM + H; e.ldgM = 2 * H;
+    e.cvec = w.cvec; e.wx = W + o.wx; e.alpha = alpha;
+    e.gz2_pk = w.gz2_pk; e.gz1_vm = w.gz1_vm;
+    e.colpart = w.partial;
+    e.g_b2 = gW + o.b2; e.g_wx = gW + o.wx; e.g_w1d = gW + o.W1 + 2 * HH;
+    HGNN_TRY(launch_edge_bwd(st, H, bf16, e));
   }
-  HGNN_TRY(launch_edge_pre(st, H, E, dst, col, d2, s.PQ, W + o.W1 + 2 * HH, w.a1, w.s1));
-  {  // gW2 = a1^T g_z2
-    WgradArgs a;
-    a.A[0] = w.a1; a.lda[0] = H;
-    a.B[0] = w.g_z2; a.ldb[0] = H;
-    a.M = E;
-    a.dest[0] = gW + o.W2;
-    a.partial = w.partial;
-    HGNN_TRY(launch_wgrad(st, H, bf16, a));
-  }
-  if (E > 0) {  // g_z1 = (g_z2 W2^T) * silu'(z1), in place over s1
-    GemmArgs g;
-    g.A[0] = w.g_z2; g.lda[0] = H;
-    g.B = w.packed; g.blk[0][0] = 3;
-    g.M = (int)E;
-    g.mul = w.s1; g.ldmul = H;
-    g.C = w.s1; g.ldc = H;
-    HGNN_TRY(launch_gemm(st, H, bf16, g));
-  }
-  float* g_z1 = w.s1;
-  HGNN_TRY(launch_segsum(st, H, N, row_ptr, nullptr, g_z1, w.g_PQ, 2 * H));       // g_P: per destination
-  HGNN_TRY(launch_segsum(st, H, N, colT_ptr, permT, g_z1, w.g_PQ + H, 2 * H));    // g_Q: per source
+  HGNN_TRY(launch_wgrad_frag(st, H, bf16, E, s.a1_pk, w.gz2_pk, w.partial, gW + o.W2));
+  HGNN_TRY(launch_segsum_vm(st, H, N, row_ptr, nullptr, w.gz1_vm, w.g_PQ, 2 * H, PT_SEGSUM_DST));     // g_P
+  HGNN_TRY(launch_segsum_vm(st, H, N, colT_ptr, permT, w.gz1_vm, w.g_PQ + H, 2 * H, PT_SEGSUM_SRC));  // g_Q
   {
-    ColsumArgs c;  // g_w1d = sum_e d2_e * g_z1_e
-    c.X = g_z1; c.ldx = H; c.w = d2; c.M = E; c.dest = gW + o.W1 + 2 * HH; c.partial = w.partial;
-    HGNN_TRY(launch_colsum(st, H, c));
     ColsumArgs c2;  // gb1 = sum_i g_P_i
     c2.X = w.g_PQ; c2.ldx = 2 * H; c2.M = N; c2.dest = gW + o.b1; c2.partial = w.partial;
     HGNN_TRY(launch_colsum(st, H, c2));

@@ -11,6 +11,7 @@
 // The cutoff test is the one fixed in include/hgnn.h: each float operation is an explicitly rounded
 // intrinsic so that the compiler cannot contract them into fused multiply-adds.
 #include "common.h"
+#include "prof.h"
 
 namespace hgnn {
 
@@ -552,31 +553,43 @@ extern "C" int32_t hgnn_radius_graph_count(void* stream, int32_t N, int32_t G, c
     HGNN_HIP(hipStreamSynchronize(st));
     return HGNN_OK;
   }
-  k_graph_meta<<<G, 64, 0, st>>>(N, G, pos, graph_off, cell, pbc, rc, w.meta, w.nbins, w.status);
-  HGNN_LAUNCH_CHECK("k_graph_meta");
-  HGNN_TRY(exclusive_scan_i32(st, w.nbins, w.bin_off, G, w.scan));
-  k_set_bin_off<<<nblk(G, 256), 256, 0, st>>>(G, w.meta, w.bin_off);
-  HGNN_LAUNCH_CHECK("k_set_bin_off");
-  // offsets must be valid before atoms are binned through them
   int32_t status_h[4] = {0, 0, 0, 0};
+  {
+    ProfScope ps(PT_NEIGH_SETUP, st);
+    k_graph_meta<<<G, 64, 0, st>>>(N, G, pos, graph_off, cell, pbc, rc, w.meta, w.nbins, w.status);
+    HGNN_LAUNCH_CHECK("k_graph_meta");
+    HGNN_TRY(exclusive_scan_i32(st, w.nbins, w.bin_off, G, w.scan));
+    k_set_bin_off<<<nblk(G, 256), 256, 0, st>>>(G, w.meta, w.bin_off);
+    HGNN_LAUNCH_CHECK("k_set_bin_off");
+  }
+  // offsets must be valid before atoms are binned through them
   HGNN_HIP(hipMemcpyAsync(status_h, w.status, sizeof(status_h), hipMemcpyDeviceToHost, st));
   HGNN_HIP(hipStreamSynchronize(st));
   HGNN_REQUIRE(!(status_h[0] & ST_BAD_OFFSETS), HGNN_ERR_BAD_OFFSETS,
                "graph_off must start at 0, be non-decreasing and end at N");
   HGNN_REQUIRE(!(status_h[0] & ST_BAD_CELL), HGNN_ERR_BAD_CELL,
                "a periodic graph has a singular cell or needs more than 127 images per direction");
-  k_fill_i32<<<nblk(w.maxbins, 256), 256, 0, st>>>(w.bin_cnt, w.maxbins, 0);
-  k_fill_i32<<<nblk(w.maxbins, 256), 256, 0, st>>>(w.bin_cur, w.maxbins, 0);
-  HGNN_LAUNCH_CHECK("k_fill_i32");
-  k_bin_atoms_count<<<nblk(N, 256), 256, 0, st>>>(N, G, pos, graph_off, w.meta, w.atom_graph, w.atom_bin, w.bin_cnt);
-  HGNN_LAUNCH_CHECK("k_bin_atoms_count");
-  HGNN_TRY(exclusive_scan_i32(st, w.bin_cnt, w.bin_start, w.maxbins, w.scan));
-  k_bin_atoms_fill<<<nblk(N, 256), 256, 0, st>>>(N, w.atom_bin, w.bin_start, w.bin_cur, w.bin_atoms);
-  HGNN_LAUNCH_CHECK("k_bin_atoms_fill");
-  k_neighbors<false><<<nblk((int64_t)N * 64, 256), 256, 0, st>>>(N, pos, w.meta, w.atom_graph, w.atom_bin, w.bin_start,
-                                                                 w.bin_atoms, rc, w.deg, nullptr, nullptr, nullptr);
-  HGNN_LAUNCH_CHECK("k_neighbors<count>");
-  HGNN_TRY(exclusive_scan_i32(st, w.deg, row_ptr, N, w.scan));
+  {
+    ProfScope ps(PT_NEIGH_SETUP, st);
+    k_fill_i32<<<nblk(w.maxbins, 256), 256, 0, st>>>(w.bin_cnt, w.maxbins, 0);
+    k_fill_i32<<<nblk(w.maxbins, 256), 256, 0, st>>>(w.bin_cur, w.maxbins, 0);
+    HGNN_LAUNCH_CHECK("k_fill_i32");
+    k_bin_atoms_count<<<nblk(N, 256), 256, 0, st>>>(N, G, pos, graph_off, w.meta, w.atom_graph, w.atom_bin, w.bin_cnt);
+    HGNN_LAUNCH_CHECK("k_bin_atoms_count");
+    HGNN_TRY(exclusive_scan_i32(st, w.bin_cnt, w.bin_start, w.maxbins, w.scan));
+    k_bin_atoms_fill<<<nblk(N, 256), 256, 0, st>>>(N, w.atom_bin, w.bin_start, w.bin_cur, w.bin_atoms);
+    HGNN_LAUNCH_CHECK("k_bin_atoms_fill");
+  }
+  {
+    ProfScope ps(PT_NEIGH_COUNT, st);
+    k_neighbors<false><<<nblk((int64_t)N * 64, 256), 256, 0, st>>>(N, pos, w.meta, w.atom_graph, w.atom_bin, w.bin_start,
+                                                                   w.bin_atoms, rc, w.deg, nullptr, nullptr, nullptr);
+    HGNN_LAUNCH_CHECK("k_neighbors<count>");
+  }
+  {
+    ProfScope ps(PT_NEIGH_SETUP, st);
+    HGNN_TRY(exclusive_scan_i32(st, w.deg, row_ptr, N, w.scan));
+  }
   // grand total (int64) sits behind the block sums of the last scan
   int64_t nbs = ((int64_t)N + SCAN_BLK - 1) / SCAN_BLK;
   long long total = 0;
@@ -604,24 +617,28 @@ extern "C" int32_t hgnn_radius_graph_fill(void* stream, int32_t N, int32_t G, co
   NeighWs w = carve_neigh(ws, N, G);
   HGNN_REQUIRE(ws_bytes >= w.bytes, HGNN_ERR_WORKSPACE_TOO_SMALL, "radius graph workspace too small");
   HGNN_REQUIRE(tmp_bytes >= (size_t)E * 8, HGNN_ERR_WORKSPACE_TOO_SMALL, "radius graph tmp: need %zu bytes", (size_t)E * 8);
-  if (G > 0 || N == 0) {
-    if (N == 0) {
-      k_fill_i32<<<nblk(G + 1, 256), 256, 0, st>>>(edge_graph_ptr, G + 1, 0);
-      k_fill_i32<<<1, 64, 0, st>>>(colT_ptr, 1, 0);
-      HGNN_LAUNCH_CHECK("k_fill_i32");
-      return HGNN_OK;
-    }
+  if (N == 0) {
+    k_fill_i32<<<nblk(G + 1, 256), 256, 0, st>>>(edge_graph_ptr, G + 1, 0);
+    k_fill_i32<<<1, 64, 0, st>>>(colT_ptr, 1, 0);
+    HGNN_LAUNCH_CHECK("k_fill_i32");
+    return HGNN_OK;
   }
   int32_t* key_j = static_cast<int32_t*>(tmp);
   int32_t* key_c = key_j + E;
   if (E > 0) {
-    k_neighbors<true><<<nblk((int64_t)N * 64, 256), 256, 0, st>>>(N, pos, w.meta, w.atom_graph, w.atom_bin, w.bin_start,
-                                                                  w.bin_atoms, rc, nullptr, row_ptr, key_j, key_c);
-    HGNN_LAUNCH_CHECK("k_neighbors<fill>");
+    {
+      ProfScope ps(PT_NEIGH_FILL, st);
+      k_neighbors<true><<<nblk((int64_t)N * 64, 256), 256, 0, st>>>(N, pos, w.meta, w.atom_graph, w.atom_bin,
+                                                                    w.bin_start, w.bin_atoms, rc, nullptr, row_ptr,
+                                                                    key_j, key_c);
+      HGNN_LAUNCH_CHECK("k_neighbors<fill>");
+    }
+    ProfScope ps(PT_NEIGH_EMIT, st);
     k_emit_rows<<<nblk((int64_t)N * 64, 256), 256, 0, st>>>(N, pos, w.meta, w.atom_graph, row_ptr, key_j, key_c, dst, col,
                                                             shift, d2, rvec);
     HGNN_LAUNCH_CHECK("k_emit_rows");
   }
+  ProfScope pst(PT_NEIGH_TRANSPOSE, st);
   k_edge_graph_ptr<<<nblk(G + 1, 256), 256, 0, st>>>(G, graph_off, row_ptr, edge_graph_ptr);
   HGNN_LAUNCH_CHECK("k_edge_graph_ptr");
   // transpose plan

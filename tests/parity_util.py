@@ -74,3 +74,11 @@ def assert_graph_equal(got, want):
     # float outputs are produced by the same individually rounded float32 operations: bit-exact
     assert np.array_equal(got["d2"].view(np.uint32), want["d2"].view(np.uint32)), "d2"
     assert np.array_equal(got["rvec"].view(np.uint32), want["rvec"].view(np.uint32)), "rvec"
+
+
+def sub_batch(b, graphs):
+    """The listed graphs of a batch as a batch of their own (same atoms, cells, sources)."""
+    from hgnn_inputs import concat_graphs
+    gl = [(b.pos[b.graph_off[g]:b.graph_off[g + 1]], b.Z[b.graph_off[g]:b.graph_off[g + 1]],
+           b.cell[g] if b.pbc[g] else None) for g in graphs]
+    return concat_graphs(gl, b.source_id[graphs])

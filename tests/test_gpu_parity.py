@@ -9,7 +9,7 @@ from hgnn_inputs import concat_graphs, make_config, small_mixed_batch
 from hgnn_inputs.structures import make_crystal, make_cubic_bulk
 
 from parity_util import (TOL, assert_graph_equal, gpu_hotpath, oracle_graph, oracle_step,
-                         problem_from_batch, problem_from_config, relerr)
+                         problem_from_batch, problem_from_config, relerr, sub_batch)
 
 pytestmark = pytest.mark.gpu
 
@@ -266,12 +266,6 @@ def test_step_is_bitwise_reproducible():
 # ------------------------------------------------------------------------------------------------
 # full sizes, in the launch configuration bench.py times
 # ------------------------------------------------------------------------------------------------
-def sub_batch(b, graphs):
-    gl = [(b.pos[b.graph_off[g]:b.graph_off[g + 1]], b.Z[b.graph_off[g]:b.graph_off[g + 1]],
-           b.cell[g] if b.pbc[g] else None) for g in graphs]
-    return concat_graphs(gl, b.source_id[graphs])
-
-
 def test_full_size_cfg4_sampled_graphs():
     """Config 4 (~40k atoms, ~1.2M edges, bf16, 5 sources). A graph's outputs depend on that graph
     only, so the oracle recomputes sampled graphs one sub-batch at a time."""
