@@ -98,12 +98,16 @@ int32_t hgnn_radius_graph_fill(void* stream, int32_t N, int32_t G,
 
 /* ---------------------------------------------------------------------------------------------
  * Embedding: h0[i,:] = emb[Z[i],:]  (input node features = learnable table indexed by atomic
- * number, 0 <= Z <= HGNN_ZMAX). _bwd: g_emb[z,:] = sum over atoms with Z == z of g_h[i,:].
+ * number, 0 <= Z <= HGNN_ZMAX). _bwd: g_emb[z,:] = sum over atoms with Z == z of g_h[i,:], summed in
+ * atom order (chunks of atoms are reduced first, then the chunks in order); ws is scratch of
+ * hgnn_embed_bwd_workspace_bytes(N, H) bytes.
  * ------------------------------------------------------------------------------------------- */
 int32_t hgnn_embed_fwd(void* stream, int32_t N, int32_t H, const int32_t* Z,
                        const float* emb /*[ZMAX+1,H]*/, float* h /*out [N,H]*/);
+int32_t hgnn_embed_bwd_workspace_bytes(int32_t N, int32_t H, size_t* ws_bytes_host);
 int32_t hgnn_embed_bwd(void* stream, int32_t N, int32_t H, const int32_t* Z,
-                       const float* g_h /*[N,H]*/, float* g_emb /*out [ZMAX+1,H]*/);
+                       const float* g_h /*[N,H]*/, float* g_emb /*out [ZMAX+1,H]*/,
+                       void* ws, size_t ws_bytes);
 
 /* ---------------------------------------------------------------------------------------------
  * One message-passing layer of the shared stack (EGNN layer, positions held fixed):

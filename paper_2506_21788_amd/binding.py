@@ -19,7 +19,7 @@ ZMAX = 94
 EXPORTS = [
     "hgnn_last_error_string", "hgnn_version",
     "hgnn_radius_graph_workspace_bytes", "hgnn_radius_graph_count", "hgnn_radius_graph_fill",
-    "hgnn_embed_fwd", "hgnn_embed_bwd",
+    "hgnn_embed_fwd", "hgnn_embed_bwd", "hgnn_embed_bwd_workspace_bytes",
     "hgnn_mp_layer_workspace_bytes", "hgnn_mp_layer_fwd", "hgnn_mp_layer_bwd",
     "hgnn_pool_by_graph_fwd", "hgnn_pool_by_graph_bwd",
     "hgnn_multihead_plan_ints", "hgnn_multihead_plan",
@@ -63,7 +63,8 @@ _rg_count = _sig("hgnn_radius_graph_count", vp, i32, i32, vp, vp, vp, vp, f32, v
 _rg_fill = _sig("hgnn_radius_graph_fill", vp, i32, i32, vp, vp, vp, vp, f32, vp, sz, vp, sz, vp, i64,
                 vp, vp, vp, vp, vp, vp, vp, vp)
 _embed_fwd = _sig("hgnn_embed_fwd", vp, i32, i32, vp, vp, vp)
-_embed_bwd = _sig("hgnn_embed_bwd", vp, i32, i32, vp, vp, vp)
+_embed_bwd = _sig("hgnn_embed_bwd", vp, i32, i32, vp, vp, vp, vp, sz)
+_embed_bwd_ws = _sig("hgnn_embed_bwd_workspace_bytes", i32, i32, C.POINTER(sz))
 _mp_ws = _sig("hgnn_mp_layer_workspace_bytes", i32, i64, i32, i32, C.POINTER(sz), C.POINTER(sz))
 _mp_fwd = _sig("hgnn_mp_layer_fwd", vp, i32, i64, i32, i32, f32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
                vp, sz, vp, sz)
@@ -133,8 +134,14 @@ def embed_fwd(N, H, Z, emb, h):
     _check(_embed_fwd(_stream(), N, H, _p(Z), _p(emb), _p(h)))
 
 
-def embed_bwd(N, H, Z, g_h, g_emb):
-    _check(_embed_bwd(_stream(), N, H, _p(Z), _p(g_h), _p(g_emb)))
+def embed_bwd_workspace_bytes(N, H):
+    b = sz(0)
+    _check(_embed_bwd_ws(N, H, C.byref(b)))
+    return b.value
+
+
+def embed_bwd(N, H, Z, g_h, g_emb, ws):
+    _check(_embed_bwd(_stream(), N, H, _p(Z), _p(g_h), _p(g_emb), _p(ws), _nbytes(ws)))
 
 
 def mp_layer_workspace_bytes(N, E, H, dtype):

@@ -27,14 +27,14 @@ __device__ __forceinline__ void silu_both(float t, float& y, float& dy) {
   dy = s * (1.0f + t * (1.0f - s));
 }
 
-// float -> bf16 bits, round to nearest even (inputs are finite)
-__device__ __forceinline__ unsigned f2bf_bits(float x) {
-  unsigned u = __float_as_uint(x);
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return u >> 16;
-}
+// float -> bf16, round to nearest even, through the packed hardware conversion (v_cvt_pk_bf16_f32)
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ unsigned pack_bf16x2(float lo, float hi) {
-  return f2bf_bits(lo) | (f2bf_bits(hi) << 16);
+  const f32x2_t v = {lo, hi};
+  const bf16x2_t b = __builtin_convertvector(v, bf16x2_t);
+  return *reinterpret_cast<const unsigned*>(&b);
 }
+__device__ __forceinline__ unsigned f2bf_bits(float x) { return pack_bf16x2(x, 0.f) & 0xffffu; }
 
 }  // namespace hgnn

@@ -19,11 +19,16 @@ namespace hgnn {
 
 inline size_t frag_rows(int64_t E) { return (size_t)((E + 31) / 32 * 32); }
 
+// With bf16 operands and H = 256 each lane of the fused kernels owns two 32-column blocks (2*wc and
+// 2*wc+1); node tensors they gather are then stored as bf16 PAIRS: 32-bit word (wc*32 + x) of a row
+// holds columns wc*64 + x (low half) and wc*64 + 32 + x (high half).
+inline bool edge_pairs(int H, bool bf16) { return bf16 && H == 256; }
+
 struct EdgeFwdArgs {
   int64_t E;
   const int32_t *dst, *col;
   const float* d2;
-  const float* PQ;     // [N,2H]: P = h W1a + b1 | Q = h W1b
+  const void* PQ;      // [N,2H] fp32: P = h W1a + b1 | Q = h W1b; or bf16 pairs (see edge_pairs())
   const float* w1d;    // [H]
   const void* W2p;     // packed W2 block
   const float* b2;     // [H]
@@ -41,11 +46,11 @@ struct EdgeBwdArgs {
   int64_t E;
   const int32_t *dst, *col;
   const float* d2;
-  const float* PQ;
+  const void* PQ;      // as in the forward kernel
   const float* w1d;
   const void* W2Tp;    // packed W2^T block
   const void* z2_vm;   // saved by the forward kernel
-  const float* gM;     // [N, ldgM] gradient of the aggregated messages
+  const void* gM;      // gradient of the aggregated messages: fp32 [N, ldgM], or bf16 pairs [N, ldgM words]
   int ldgM;
   const float* cvec;   // [E] c_e = alpha * (g_v[dst[e]] . rvec[e])
   const float* wx;     // [H]

@@ -62,26 +62,52 @@ __device__ __forceinline__ void load4(const float* __restrict__ p, int64_t e4, i
   }
 }
 
-// store 16 accumulator-mapped values of one 32x32 block in operand-packed order
-template <bool BF16>
-__device__ __forceinline__ void store_packed(void* base, size_t blk, int lane, const float* vals) {
+// 8 accumulator-mapped values of one half of a 32x32 block (column n of the tile, registers v = 8*vh .. 8*vh+7,
+// rows rbase + 8*(v>>2) + 4g + (v&3)): written row-major into the LDS tile and, operand-packed, to memory.
+// bf16 values are converted once.
+template <bool BF16, int STRIDE>
+__device__ __forceinline__ void emit_half(unsigned char* smem, int rbase, int g, int n, const float* vals, int vh,
+                                          void* packed, size_t blk, int lane) {
   if (BF16) {
-    uint4* p = reinterpret_cast<uint4*>(base) + blk * 2 * 64 + lane;
+    unsigned pk[4];
+    unsigned short* s16 = reinterpret_cast<unsigned short*>(smem);
 #pragma unroll
-    for (int vh = 0; vh < 2; ++vh) {
-      uint4 w;
-      w.x = pack_bf16x2(vals[vh * 8 + 0], vals[vh * 8 + 1]);
-      w.y = pack_bf16x2(vals[vh * 8 + 2], vals[vh * 8 + 3]);
-      w.z = pack_bf16x2(vals[vh * 8 + 4], vals[vh * 8 + 5]);
-      w.w = pack_bf16x2(vals[vh * 8 + 6], vals[vh * 8 + 7]);
-      p[vh * 64] = w;
+    for (int t = 0; t < 4; ++t) {
+      pk[t] = pack_bf16x2(vals[2 * t], vals[2 * t + 1]);
+      const int row = rbase + 8 * (2 * vh + (t >> 1)) + 4 * g + 2 * (t & 1);
+      s16[row * STRIDE + n] = (unsigned short)(pk[t] & 0xffffu);
+      s16[(row + 1) * STRIDE + n] = (unsigned short)(pk[t] >> 16);
+    }
+    {
+      typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
+      const u32x4_t w = {pk[0], pk[1], pk[2], pk[3]};
+      __builtin_nontemporal_store(w, reinterpret_cast<u32x4_t*>(packed) + (blk * 2 + vh) * 64 + lane);
     }
   } else {
-    float4* p = reinterpret_cast<float4*>(base) + blk * 4 * 64 + lane;
+    float* s32 = reinterpret_cast<float*>(smem);
 #pragma unroll
-    for (int vq = 0; vq < 4; ++vq)
-      p[vq * 64] = make_float4(vals[vq * 4], vals[vq * 4 + 1], vals[vq * 4 + 2], vals[vq * 4 + 3]);
+    for (int u = 0; u < 8; ++u) s32[(rbase + 8 * (2 * vh + (u >> 2)) + 4 * g + (u & 3)) * STRIDE + n] = vals[u];
+    f32x4_t* p = reinterpret_cast<f32x4_t*>(packed) + (blk * 4 + 2 * vh) * 64 + lane;
+    const f32x4_t w0 = {vals[0], vals[1], vals[2], vals[3]};
+    const f32x4_t w1 = {vals[4], vals[5], vals[6], vals[7]};
+    __builtin_nontemporal_store(w0, p);
+    __builtin_nontemporal_store(w1, p + 64);
   }
+}
+
+// persistent tile loop that keeps each XCD (workgroups are dealt to the 8 XCDs round-robin) on its own
+// contiguous eighth of the tiles, so that the node rows an XCD gathers stay in that XCD's L2
+struct TileRange {
+  int first, end, step;
+};
+__device__ __forceinline__ TileRange xcd_tile_range(int ntiles) {
+  const int G = gridDim.x;
+  if ((G & 7) != 0 || ntiles < 64) return {(int)blockIdx.x, ntiles, G};
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int per = (ntiles + 7) >> 3;
+  const int lo = xcd * per;
+  const int hi = lo + per < ntiles ? lo + per : ntiles;
+  return {lo + slot, hi, G >> 3};
 }
 
 // A tile (LDS, row-major, padded) x packed B block -> accumulators; same tiling as the row-tile GEMM
@@ -133,19 +159,139 @@ __device__ __forceinline__ void tile_mma(const unsigned char* smem, const void* 
   }
 }
 
-template <bool BF16>
-__device__ __forceinline__ void lds_put(unsigned char* smem, int idx, float v) {
-  if (BF16) reinterpret_cast<unsigned short*>(smem)[idx] = (unsigned short)f2bf_bits(v);
-  else reinterpret_cast<float*>(smem)[idx] = v;
+// Same product with this wavefront's slice of B held in registers for the whole kernel.
+template <int H, bool BF16>
+struct BFrag {
+  using type = float4;
+  static constexpr int NKB = H / 8;
+};
+template <int H>
+struct BFrag<H, true> {
+  using type = bf16x8_t;
+  static constexpr int NKB = H / 16;
+};
+
+template <int H, bool BF16>
+__device__ __forceinline__ void load_b_resident(const void* Bpacked, int wc, int lane,
+                                                typename BFrag<H, BF16>::type (&breg)[BFrag<H, BF16>::NKB][ECfg<H, BF16>::CB]) {
+  using C = ECfg<H, BF16>;
+  using T = typename BFrag<H, BF16>::type;
+  constexpr int NKB = BFrag<H, BF16>::NKB;
+  const T* __restrict__ Bp = reinterpret_cast<const T*>(Bpacked);
+#pragma unroll
+  for (int kb = 0; kb < NKB; ++kb)
+#pragma unroll
+    for (int j = 0; j < C::CB; ++j) breg[kb][j] = Bp[((wc * C::CB + j) * NKB + kb) * 64 + lane];
+}
+
+template <int H, bool BF16>
+__device__ __forceinline__ void tile_mma_res(const unsigned char* smem, int wr, int lane,
+                                             const typename BFrag<H, BF16>::type (&breg)[BFrag<H, BF16>::NKB][ECfg<H, BF16>::CB],
+                                             f32x16_t (&acc)[ECfg<H, BF16>::RB][ECfg<H, BF16>::CB]) {
+  using C = ECfg<H, BF16>;
+  constexpr int NKB = BFrag<H, BF16>::NKB;
+#pragma unroll
+  for (int kb = 0; kb < NKB; ++kb) {
+    if constexpr (BF16) {
+      bf16x8_t a[C::RB];
+#pragma unroll
+      for (int i = 0; i < C::RB; ++i) {
+        const int row = (wr * C::RB + i) * 32 + (lane & 31);
+        a[i] = *reinterpret_cast<const bf16x8_t*>(smem + ((size_t)row * C::STRIDE + kb * 16 + (lane >> 5) * 8) * 2);
+      }
+#pragma unroll
+      for (int j = 0; j < C::CB; ++j)
+#pragma unroll
+        for (int i = 0; i < C::RB; ++i)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], breg[kb][j], acc[i][j], 0, 0, 0);
+    } else {
+      float4 a[C::RB];
+#pragma unroll
+      for (int i = 0; i < C::RB; ++i) {
+        const int row = (wr * C::RB + i) * 32 + (lane & 31);
+        a[i] = *reinterpret_cast<const float4*>(smem + ((size_t)row * C::STRIDE + kb * 8 + (lane >> 5) * 4) * 4);
+      }
+#pragma unroll
+      for (int j = 0; j < C::CB; ++j)
+#pragma unroll
+        for (int i = 0; i < C::RB; ++i) {
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].x, breg[kb][j].x, acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].y, breg[kb][j].y, acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].z, breg[kb][j].z, acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].w, breg[kb][j].w, acc[i][j], 0, 0, 0);
+        }
+    }
+  }
+}
+
+// Per-edge scalars of a tile (dst | col | d2 bits), fetched one tile ahead into LDS: element tid of [3][TM]
+template <int TM>
+__device__ __forceinline__ int fetch_edge_scalar(const int32_t* __restrict__ dst, const int32_t* __restrict__ col,
+                                                 const float* __restrict__ d2, int tile, int tile_end, int64_t E,
+                                                 int tid) {
+  const int which = tid / TM, r = tid - which * TM;
+  const int64_t e = (int64_t)tile * TM + r;
+  if (tid >= 3 * TM || tile >= tile_end || e >= E) return 0;
+  return which == 0 ? dst[e] : (which == 1 ? col[e] : __float_as_int(d2[e]));
+}
+
+// z1 = P[dst] + Q[col] + d2*w1d for 8 edges and this lane's CB column blocks.
+// PAIRS: the projected features are stored as bf16 pairs, one 32-bit word holding this lane's two
+// columns (block 2*wc and block 2*wc+1) of P or Q; a row is [H/2 words of P | H/2 words of Q].
+template <int H, int CB, bool PAIRS>
+__device__ __forceinline__ void gather_z1(const void* __restrict__ PQ, const int* di, const int* ci, const float* dd,
+                                          const float* w1d, int wc, int x, float (&z)[CB][8]) {
+  if constexpr (PAIRS) {
+    static_assert(CB == 2, "pair storage needs two column blocks per lane");
+    const unsigned* __restrict__ U = reinterpret_cast<const unsigned*>(PQ);
+    const int wcol = wc * 32 + x;
+    unsigned wp[8], wq[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      wp[u] = U[di[u] * H + wcol];
+      wq[u] = U[ci[u] * H + (H / 2) + wcol];
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      z[0][u] = __uint_as_float(wp[u] << 16) + __uint_as_float(wq[u] << 16) + dd[u] * w1d[0];
+      z[1][u] = __uint_as_float(wp[u] & 0xffff0000u) + __uint_as_float(wq[u] & 0xffff0000u) + dd[u] * w1d[1];
+    }
+  } else {
+    const float* __restrict__ F = reinterpret_cast<const float*>(PQ);
+#pragma unroll
+    for (int j = 0; j < CB; ++j) {
+      const int n = (wc * CB + j) * 32 + x;
+      float a[8], b[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        a[u] = F[di[u] * 2 * H + n];
+        b[u] = F[ci[u] * 2 * H + H + n];
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) z[j][u] = a[u] + b[u] + dd[u] * w1d[j];
+    }
+  }
+}
+
+// the 8 per-edge scalars of rows rblk*32 + 8*(2*vh + jj) + 4*g + ii (jj < 2, ii < 4) from an LDS array
+__device__ __forceinline__ void lds_rows8(const int* s, int rblk, int vh, int g, int* o) {
+#pragma unroll
+  for (int jj = 0; jj < 2; ++jj) {
+    const int4 t = *reinterpret_cast<const int4*>(s + rblk * 32 + 8 * (2 * vh + jj) + 4 * g);
+    o[4 * jj + 0] = t.x; o[4 * jj + 1] = t.y; o[4 * jj + 2] = t.z; o[4 * jj + 3] = t.w;
+  }
 }
 
 // ---------------------------------------------------------------------------------------------
 // forward
 // ---------------------------------------------------------------------------------------------
-template <int H, bool BF16>
-__global__ void __launch_bounds__(256) k_edge_fwd(EdgeFwdArgs p, int ntiles) {
+template <int H, bool BF16, bool BRES_REQ>
+__global__ void __launch_bounds__(256, 2) k_edge_fwd(EdgeFwdArgs p, int ntiles) {
   using C = ECfg<H, BF16>;
+  constexpr bool BRES = BRES_REQ && (BF16 || H <= 128);   // keep this wavefront's slice of W2 in registers?
+  constexpr bool PAIRS = BF16 && C::CB == 2;
   extern __shared__ __align__(16) unsigned char smem[];
+  int* sc = reinterpret_cast<int*>(smem + C::LDS_BYTES);   // [2][3][TM] per-edge scalars, double buffered
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wr = wave / C::WC, wc = wave % C::WC;
   const int g = lane >> 5, x = lane & 31;
@@ -157,44 +303,50 @@ __global__ void __launch_bounds__(256) k_edge_fwd(EdgeFwdArgs p, int ntiles) {
     w1d[j] = p.w1d[n];
     b2[j] = p.b2[n];
   }
-  for (int tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
-    // ---- produce a1 for this wavefront's blocks: global (operand-packed) and LDS (row-major)
+  typename BFrag<H, BF16>::type breg[BRES ? BFrag<H, BF16>::NKB : 1][C::CB];
+  if constexpr (BRES) load_b_resident<H, BF16>(p.W2p, wc, lane, breg);
+  const TileRange tr = xcd_tile_range(ntiles);
+  {
+    const int s0 = fetch_edge_scalar<C::TM>(p.dst, p.col, p.d2, tr.first, tr.end, E, tid);
+    if (tid < 3 * C::TM) sc[tid] = s0;
+  }
+  __syncthreads();
+  int buf = 0;
+  for (int tile = tr.first; tile < tr.end; tile += tr.step, buf ^= 1) {
+    // the next tile's scalars travel while this tile is processed
+    const int nxt = fetch_edge_scalar<C::TM>(p.dst, p.col, p.d2, tile + tr.step, tr.end, E, tid);
+    const int* s = sc + buf * 3 * C::TM;
+    // ---- produce a1 for this wavefront's blocks: memory (operand-packed) and LDS (row-major)
 #pragma unroll
     for (int i = 0; i < C::RB; ++i) {
       const int rblk = wr * C::RB + i;
       const int64_t eb = (int64_t)tile * (C::TM / 32) + rblk;
       if (eb * 32 >= E) continue;
-      int po[16], qo[16];
-      float dd[16];
-      unsigned ok = 0;
 #pragma unroll
-      for (int jj = 0; jj < 4; ++jj) {
-        const int64_t e4 = eb * 32 + 8 * jj + 4 * g;
-        int di[4], ci[4];
-        load4(p.dst, e4, E, di);
-        load4(p.col, e4, E, ci);
-        load4(p.d2, e4, E, &dd[4 * jj]);
+      for (int vh = 0; vh < 2; ++vh) {
+        int di[8], ci[8], dbits[8];
+        float dd[8];
+        lds_rows8(s, rblk, vh, g, di);
+        lds_rows8(s + C::TM, rblk, vh, g, ci);
+        lds_rows8(s + 2 * C::TM, rblk, vh, g, dbits);
+        unsigned ok = 0;
 #pragma unroll
-        for (int ii = 0; ii < 4; ++ii) {
-          po[4 * jj + ii] = di[ii] * 2 * H;
-          qo[4 * jj + ii] = ci[ii] * 2 * H + H;
-          ok |= (e4 + ii < E ? 1u : 0u) << (4 * jj + ii);
+        for (int u = 0; u < 8; ++u) {
+          dd[u] = __int_as_float(dbits[u]);
+          const int64_t e = eb * 32 + 8 * (2 * vh + (u >> 2)) + 4 * g + (u & 3);
+          ok |= (e < E ? 1u : 0u) << u;
         }
-      }
+        float z[C::CB][8];
+        gather_z1<H, C::CB, PAIRS>(p.PQ, di, ci, dd, w1d, wc, x, z);
 #pragma unroll
-      for (int j = 0; j < C::CB; ++j) {
-        const int cblk = wc * C::CB + j;
-        const int n = cblk * 32 + x;
-        float vals[16];
+        for (int j = 0; j < C::CB; ++j) {
+          const int cblk = wc * C::CB + j;
+          const int n = cblk * 32 + x;
+          float vals[8];
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const float z = p.PQ[po[v] + n] + p.PQ[qo[v] + n] + dd[v] * w1d[j];
-          const float a = ((ok >> v) & 1u) ? silu_f(z) : 0.f;
-          vals[v] = a;
-          const int row = rblk * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
-          lds_put<BF16>(smem, row * C::STRIDE + n, a);
+          for (int u = 0; u < 8; ++u) vals[u] = ((ok >> u) & 1u) ? silu_f(z[j][u]) : 0.f;
+          emit_half<BF16, C::STRIDE>(smem, rblk * 32, g, n, vals, vh, p.a1_pk, (size_t)eb * C::NCB + cblk, lane);
         }
-        store_packed<BF16>(p.a1_pk, (size_t)eb * C::NCB + cblk, lane, vals);
       }
     }
     __syncthreads();
@@ -205,7 +357,9 @@ __global__ void __launch_bounds__(256) k_edge_fwd(EdgeFwdArgs p, int ntiles) {
       for (int j = 0; j < C::CB; ++j)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-    tile_mma<H, BF16>(smem, p.W2p, wr, wc, lane, acc);
+    if constexpr (BRES) tile_mma_res<H, BF16>(smem, wr, lane, breg, acc);
+    else tile_mma<H, BF16>(smem, p.W2p, wr, wc, lane, acc);
+    if (tid < 3 * C::TM) sc[(buf ^ 1) * 3 * C::TM + tid] = nxt;
     __syncthreads();
     // ---- z2 = acc + b2, stored v-major
 #pragma unroll
@@ -215,11 +369,18 @@ __global__ void __launch_bounds__(256) k_edge_fwd(EdgeFwdArgs p, int ntiles) {
 #pragma unroll
       for (int j = 0; j < C::CB; ++j) {
         const size_t base = (((size_t)eb * C::NCB + (wc * C::CB + j)) * 16) * 64 + lane;
+        if (BF16) {
+          unsigned short* o = reinterpret_cast<unsigned short*>(p.z2_vm) + base;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const float z = acc[i][j][v] + b2[j];
-          if (BF16) reinterpret_cast<unsigned short*>(p.z2_vm)[base + v * 64] = (unsigned short)f2bf_bits(z);
-          else reinterpret_cast<float*>(p.z2_vm)[base + v * 64] = z;
+          for (int t = 0; t < 8; ++t) {
+            const unsigned pk = pack_bf16x2(acc[i][j][2 * t] + b2[j], acc[i][j][2 * t + 1] + b2[j]);
+            __builtin_nontemporal_store((unsigned short)(pk & 0xffffu), o + (2 * t) * 64);
+            __builtin_nontemporal_store((unsigned short)(pk >> 16), o + (2 * t + 1) * 64);
+          }
+        } else {
+          float* o = reinterpret_cast<float*>(p.z2_vm) + base;
+#pragma unroll
+          for (int v = 0; v < 16; ++v) __builtin_nontemporal_store(acc[i][j][v] + b2[j], o + v * 64);
         }
       }
     }
@@ -233,14 +394,14 @@ static int32_t launch_edge_fwd_t(hipStream_t st, const EdgeFwdArgs& a) {
   if (ntiles <= 0) return HGNN_OK;
   static bool attr_set = false;
   if (!attr_set) {
-    HGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_edge_fwd<H, BF16>),
-                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES));
+    HGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_edge_fwd<H, BF16, true>),
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)(C::LDS_BYTES + 6 * C::TM * 4)));
     attr_set = true;
   }
   int64_t grid = (int64_t)num_cus() * 4;
   if (grid > ntiles) grid = ntiles;
   ProfScope ps(PT_EDGE_FUSED_FWD, st);
-  k_edge_fwd<H, BF16><<<dim3((unsigned)grid), 256, C::LDS_BYTES, st>>>(a, (int)ntiles);
+  k_edge_fwd<H, BF16, true><<<dim3((unsigned)grid), 256, C::LDS_BYTES + 6 * C::TM * 4, st>>>(a, (int)ntiles);
   HGNN_LAUNCH_CHECK("k_edge_fwd");
   return HGNN_OK;
 }
@@ -400,6 +561,7 @@ int32_t launch_edge_cvec(hipStream_t st, int64_t E, const int32_t* dst, const fl
 template <int H, bool BF16>
 __global__ void __launch_bounds__(256) k_edge_bwd(EdgeBwdArgs p, int ntiles) {
   using C = ECfg<H, BF16>;
+  constexpr bool PAIRS = BF16 && C::CB == 2;
   extern __shared__ __align__(16) unsigned char smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wr = wave / C::WC, wc = wave % C::WC;
@@ -413,49 +575,65 @@ __global__ void __launch_bounds__(256) k_edge_bwd(EdgeBwdArgs p, int ntiles) {
     wxn[j] = p.wx[n];
     sb2[j] = swx[j] = sw1[j] = 0.f;
   }
-  for (int tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+  const TileRange tr = xcd_tile_range(ntiles);
+  for (int tile = tr.first; tile < tr.end; tile += tr.step) {
     // ---- g_z2 = (alpha*g_M[dst] + c*wx) * silu'(z2): operand-packed to memory, row-major to LDS
 #pragma unroll
     for (int i = 0; i < C::RB; ++i) {
       const int rblk = wr * C::RB + i;
       const int64_t eb = (int64_t)tile * (C::TM / 32) + rblk;
       if (eb * 32 >= E) continue;
-      int mo[16];
-      float cc[16];
-      unsigned ok = 0;
 #pragma unroll
-      for (int jj = 0; jj < 4; ++jj) {
-        const int64_t e4 = eb * 32 + 8 * jj + 4 * g;
-        int di[4];
-        load4(p.dst, e4, E, di);
-        load4(p.cvec, e4, E, &cc[4 * jj]);
+      for (int vh = 0; vh < 2; ++vh) {
+        int di[8];
+        float cc[8];
+        unsigned ok = 0;
 #pragma unroll
-        for (int ii = 0; ii < 4; ++ii) {
-          mo[4 * jj + ii] = di[ii] * p.ldgM;
-          ok |= (e4 + ii < E ? 1u : 0u) << (4 * jj + ii);
+        for (int jj = 0; jj < 2; ++jj) {
+          const int64_t e4 = eb * 32 + 8 * (2 * vh + jj) + 4 * g;
+          load4(p.dst, e4, E, &di[4 * jj]);
+          load4(p.cvec, e4, E, &cc[4 * jj]);
+#pragma unroll
+          for (int ii = 0; ii < 4; ++ii) ok |= (e4 + ii < E ? 1u : 0u) << (4 * jj + ii);
         }
-      }
+        float gm[C::CB][8];
+        if constexpr (PAIRS) {
+          const unsigned* __restrict__ U = reinterpret_cast<const unsigned*>(p.gM);
 #pragma unroll
-      for (int j = 0; j < C::CB; ++j) {
-        const int cblk = wc * C::CB + j;
-        const int n = cblk * 32 + x;
-        const size_t zbase = (((size_t)eb * C::NCB + cblk) * 16) * 64 + lane;
-        float vals[16];
+          for (int u = 0; u < 8; ++u) {
+            const unsigned w = U[di[u] * p.ldgM + wc * 32 + x];
+            gm[0][u] = __uint_as_float(w << 16);
+            gm[1][u] = __uint_as_float(w & 0xffff0000u);
+          }
+        } else {
+          const float* __restrict__ F = reinterpret_cast<const float*>(p.gM);
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const float z = BF16 ? bf_bits_to_f(reinterpret_cast<const unsigned short*>(p.z2_vm)[zbase + v * 64])
-                               : reinterpret_cast<const float*>(p.z2_vm)[zbase + v * 64];
-          float m, dm;
-          silu_both(z, m, dm);
-          float gz = (p.alpha * p.gM[mo[v] + n] + cc[v] * wxn[j]) * dm;
-          if (!((ok >> v) & 1u)) { gz = 0.f; m = 0.f; }
-          vals[v] = gz;
-          sb2[j] += gz;
-          swx[j] += cc[v] * m;
-          const int row = rblk * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
-          lds_put<BF16>(smem, row * C::STRIDE + n, gz);
+          for (int j = 0; j < C::CB; ++j)
+#pragma unroll
+            for (int u = 0; u < 8; ++u) gm[j][u] = F[di[u] * p.ldgM + (wc * C::CB + j) * 32 + x];
         }
-        store_packed<BF16>(p.gz2_pk, (size_t)eb * C::NCB + cblk, lane, vals);
+#pragma unroll
+        for (int j = 0; j < C::CB; ++j) {
+          const int cblk = wc * C::CB + j;
+          const int n = cblk * 32 + x;
+          const size_t zbase = (((size_t)eb * C::NCB + cblk) * 16 + 8 * vh) * 64 + lane;
+          float zz[8], vals[8];
+#pragma unroll
+          for (int u = 0; u < 8; ++u)
+            zz[u] = BF16 ? bf_bits_to_f(__builtin_nontemporal_load(reinterpret_cast<const unsigned short*>(p.z2_vm) + zbase + u * 64))
+                         : __builtin_nontemporal_load(reinterpret_cast<const float*>(p.z2_vm) + zbase + u * 64);
+#pragma unroll
+          for (int u = 0; u < 8; ++u) {
+            float m, dm;
+            silu_both(zz[u], m, dm);
+            float gz = (p.alpha * gm[j][u] + cc[u] * wxn[j]) * dm;
+            if (!((ok >> u) & 1u)) { gz = 0.f; m = 0.f; }
+            vals[u] = gz;
+            sb2[j] += gz;
+            swx[j] += cc[u] * m;
+          }
+          emit_half<BF16, C::STRIDE>(smem, rblk * 32, g, n, vals, vh, p.gz2_pk, (size_t)eb * C::NCB + cblk, lane);
+        }
       }
     }
     __syncthreads();
@@ -473,32 +651,28 @@ __global__ void __launch_bounds__(256) k_edge_bwd(EdgeBwdArgs p, int ntiles) {
     for (int i = 0; i < C::RB; ++i) {
       const int64_t eb = (int64_t)tile * (C::TM / 32) + wr * C::RB + i;
       if (eb * 32 >= E) continue;
-      int po[16], qo[16];
-      float dd[16];
 #pragma unroll
-      for (int jj = 0; jj < 4; ++jj) {
-        const int64_t e4 = eb * 32 + 8 * jj + 4 * g;
-        int di[4], ci[4];
-        load4(p.dst, e4, E, di);
-        load4(p.col, e4, E, ci);
-        load4(p.d2, e4, E, &dd[4 * jj]);
+      for (int vh = 0; vh < 2; ++vh) {
+        int di[8], ci[8];
+        float dd[8];
 #pragma unroll
-        for (int ii = 0; ii < 4; ++ii) {
-          po[4 * jj + ii] = di[ii] * 2 * H;
-          qo[4 * jj + ii] = ci[ii] * 2 * H + H;
+        for (int jj = 0; jj < 2; ++jj) {
+          const int64_t e4 = eb * 32 + 8 * (2 * vh + jj) + 4 * g;
+          load4(p.dst, e4, E, &di[4 * jj]);
+          load4(p.col, e4, E, &ci[4 * jj]);
+          load4(p.d2, e4, E, &dd[4 * jj]);
         }
-      }
+        float z[C::CB][8];
+        gather_z1<H, C::CB, PAIRS>(p.PQ, di, ci, dd, w1d, wc, x, z);
 #pragma unroll
-      for (int j = 0; j < C::CB; ++j) {
-        const int cblk = wc * C::CB + j;
-        const int n = cblk * 32 + x;
-        const size_t base = (((size_t)eb * C::NCB + cblk) * 16) * 64 + lane;
+        for (int j = 0; j < C::CB; ++j) {
+          const size_t base = (((size_t)eb * C::NCB + (wc * C::CB + j)) * 16 + 8 * vh) * 64 + lane;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const float z1 = p.PQ[po[v] + n] + p.PQ[qo[v] + n] + dd[v] * w1d[j];
-          const float gz1 = acc[i][j][v] * dsilu_f(z1);   // rows beyond E have acc == 0
-          p.gz1_vm[base + v * 64] = gz1;
-          sw1[j] += dd[v] * gz1;
+          for (int u = 0; u < 8; ++u) {
+            const float gz1 = acc[i][j][8 * vh + u] * dsilu_f(z[j][u]);   // rows beyond E have acc == 0
+            __builtin_nontemporal_store(gz1, p.gz1_vm + base + u * 64);
+            sw1[j] += dd[u] * gz1;
+          }
         }
       }
     }

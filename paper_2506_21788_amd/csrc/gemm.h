@@ -53,6 +53,12 @@ struct GemmArgs {
   float* C = nullptr;
   int ldc = 0;
   int ncb = 1;
+  // optional: column blocks in pair_cb_mask are written as bf16 pairs (see edge_pairs()) into Cpair instead of C:
+  // word (wc*32 + x) of a row at word offset pair_off[cb]; plain bias only (no mul / add) on those blocks
+  unsigned* Cpair = nullptr;
+  int ldpair = 0;
+  int pair_cb_mask = 0;
+  int pair_off[2] = {0, 0};
   int tag = PT_GEMM_NODE;  // timing class
 };
 int32_t launch_gemm(hipStream_t st, int H, bool bf16, const GemmArgs& a);

@@ -63,7 +63,7 @@ int32_t launch_pack(hipStream_t st, int H, bool bf16, const PackArgs& a, int gro
 // ---------------------------------------------------------------------------------------------
 template <int H, bool BF16>
 struct GemmCfg {
-  static constexpr int TM = BF16 ? 128 : (H == 256 ? 64 : 128);
+  static constexpr int TM = 64;
   static constexpr int WC = (H / 32 < 4) ? H / 32 : 4;   // wavefronts side by side over columns
   static constexpr int WR = 4 / WC;                      // and over rows
   static constexpr int WROWS = TM / WR;
@@ -120,24 +120,38 @@ __global__ void __launch_bounds__(256) k_gemm(GemmArgs p) {
     const float* __restrict__ A = p.A[kc];
     const int lda = p.lda[kc];
     constexpr int CH = H / 4;
-    for (int c = tid; c < C::TM * CH; c += 256) {
-      const int r = c / CH, q = c - r * CH;
-      const int pos = rbeg + r;
-      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (pos < rend) {
+    constexpr int ITER = C::TM * CH / 256;
+    constexpr int UN = ITER < 8 ? ITER : 8;
+    static_assert(ITER % UN == 0, "staging loop must divide evenly");
+    for (int it0 = 0; it0 < ITER; it0 += UN) {
+      float4 v[UN];
+      // all loads of the batch are issued before any of them is used (rows past the end are clamped, then zeroed)
+#pragma unroll
+      for (int u = 0; u < UN; ++u) {
+        const int c = tid + (it0 + u) * 256;
+        const int r = c / CH, q = c - r * CH;
+        int pos = rbeg + r;
+        pos = pos < rend ? pos : rend - 1;
         const long gr = p.row_idx ? p.row_idx[pos] : pos;
-        v = *reinterpret_cast<const float4*>(A + gr * lda + q * 4);
-        if (p.a_silu) {
-          v.x = silu_f(v.x); v.y = silu_f(v.y); v.z = silu_f(v.z); v.w = silu_f(v.w);
-        }
+        v[u] = *reinterpret_cast<const float4*>(A + gr * lda + q * 4);
       }
-      if (BF16) {
-        uint2 w;
-        w.x = pack_bf16x2(v.x, v.y);
-        w.y = pack_bf16x2(v.z, v.w);
-        *reinterpret_cast<uint2*>(smem + ((size_t)r * C::STRIDE + q * 4) * 2) = w;
-      } else {
-        *reinterpret_cast<float4*>(smem + ((size_t)r * C::STRIDE + q * 4) * 4) = v;
+#pragma unroll
+      for (int u = 0; u < UN; ++u) {
+        const int c = tid + (it0 + u) * 256;
+        const int r = c / CH, q = c - r * CH;
+        float4 w = v[u];
+        if (p.a_silu) {
+          w.x = silu_f(w.x); w.y = silu_f(w.y); w.z = silu_f(w.z); w.w = silu_f(w.w);
+        }
+        if (rbeg + r >= rend) w = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (BF16) {
+          uint2 o;
+          o.x = pack_bf16x2(w.x, w.y);
+          o.y = pack_bf16x2(w.z, w.w);
+          *reinterpret_cast<uint2*>(smem + ((size_t)r * C::STRIDE + q * 4) * 2) = o;
+        } else {
+          *reinterpret_cast<float4*>(smem + ((size_t)r * C::STRIDE + q * 4) * 4) = w;
+        }
       }
     }
     __syncthreads();
@@ -146,7 +160,7 @@ __global__ void __launch_bounds__(256) k_gemm(GemmArgs p) {
     if (BF16) {
       const bf16x8_t* __restrict__ Bp = reinterpret_cast<const bf16x8_t*>(p.B) + bblk0 * (H * H / 8);
       constexpr int NKB = H / 16;
-#pragma unroll 4
+#pragma unroll 8
       for (int kb = 0; kb < NKB; ++kb) {
         bf16x8_t a[C::RB];
 #pragma unroll
@@ -192,6 +206,27 @@ __global__ void __launch_bounds__(256) k_gemm(GemmArgs p) {
 
   // ---- epilogue on the accumulator registers
   const bool use_bias = p.bias && ((p.bias_cb_mask >> cb) & 1);
+  if constexpr (C::CB == 2) {
+    if ((p.pair_cb_mask >> cb) & 1) {   // bf16 pairs: this lane's two column blocks share one 32-bit word
+      const int c0 = wc * C::WCOLS + (lane & 31);
+      const float b0 = use_bias ? p.bias[grp * p.grp_bias_stride + c0] : 0.f;
+      const float b1 = use_bias ? p.bias[grp * p.grp_bias_stride + c0 + 32] : 0.f;
+#pragma unroll
+      for (int i = 0; i < C::RB; ++i) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int r = wr * C::WROWS + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+          const int pos = rbeg + r;
+          if (pos < rend) {
+            const long gr = p.row_idx ? p.row_idx[pos] : pos;
+            p.Cpair[gr * p.ldpair + p.pair_off[cb] + wc * 32 + (lane & 31)] =
+                pack_bf16x2(acc[i][0][v] + b0, acc[i][1][v] + b1);
+          }
+        }
+      }
+      return;
+    }
+  }
 #pragma unroll
   for (int j = 0; j < C::CB; ++j) {
     const int col = wc * C::WCOLS + j * 32 + (lane & 31);
@@ -238,7 +273,8 @@ static int32_t launch_gemm_t(hipStream_t st, const GemmArgs& a) {
 
 int32_t launch_gemm(hipStream_t st, int H, bool bf16, const GemmArgs& a) {
   HGNN_REQUIRE(a.nkc >= 1 && a.nkc <= 2 && a.ncb >= 1 && a.ncb <= 2, HGNN_ERR_BAD_SHAPE, "gemm: bad chunk counts");
-  HGNN_REQUIRE(a.A[0] && a.B && a.C, HGNN_ERR_NULLPTR, "gemm: null operand");
+  HGNN_REQUIRE(a.A[0] && a.B && (a.C || a.Cpair), HGNN_ERR_NULLPTR, "gemm: null operand");
+  HGNN_REQUIRE(a.pair_cb_mask == 0 || (H == 256 && a.Cpair), HGNN_ERR_BAD_SHAPE, "gemm: pair output needs H = 256");
   switch (H) {
     case 64: return bf16 ? launch_gemm_t<64, true>(st, a) : launch_gemm_t<64, false>(st, a);
     case 128: return bf16 ? launch_gemm_t<128, true>(st, a) : launch_gemm_t<128, false>(st, a);
@@ -265,8 +301,17 @@ __global__ void k_reduce_partials(ReduceArgs a) {
   if (i >= a.blk_elems) return;
   const float* p = a.partial + ((long)grp * a.nsplit * a.nblk + blk) * a.blk_elems + i;
   const long step = (long)a.nblk * a.blk_elems;
+  // ascending order of the partials is kept; sixteen loads are in flight at a time
   float s = 0.f;
-  for (int k = 0; k < a.nsplit; ++k) s += p[k * step];
+  int k = 0;
+  for (; k + 16 <= a.nsplit; k += 16) {
+    float v[16];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) v[u] = p[(long)(k + u) * step];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) s += v[u];
+  }
+  for (; k < a.nsplit; ++k) s += p[(long)k * step];
   a.dest[blk][grp * a.grp_dest_stride + i] = s;
 }
 
@@ -332,17 +377,27 @@ __global__ void __launch_bounds__(256) k_wgrad(WgradArgs p, int nsplit, int rows
   constexpr int CH = C::OT / 4;
   for (long r0 = rbeg; r0 < rend; r0 += WG_RC) {
     __syncthreads();
-    for (int c = tid; c < WG_RC * CH; c += 256) {
+    constexpr int ITER = WG_RC * CH / 256;   // 1, 2 or 4
+    float4 va[ITER], vb[ITER];
+#pragma unroll
+    for (int u = 0; u < ITER; ++u) {
+      const int c = tid + u * 256;
       const int r = c / CH, q = c - r * CH;
-      float4 va = make_float4(0.f, 0.f, 0.f, 0.f), vb = va;
-      if (r0 + r < rend) {
-        const long gr = p.row_idx ? p.row_idx[r0 + r] : (r0 + r);
-        va = *reinterpret_cast<const float4*>(A + gr * lda + ta * C::OT + q * 4);
-        vb = *reinterpret_cast<const float4*>(B + gr * ldb + tb * C::OT + q * 4);
-        if (p.a_silu) { va.x = silu_f(va.x); va.y = silu_f(va.y); va.z = silu_f(va.z); va.w = silu_f(va.w); }
-      }
-      *reinterpret_cast<float4*>(&sA[r * C::STRIDE + q * 4]) = va;
-      *reinterpret_cast<float4*>(&sB[r * C::STRIDE + q * 4]) = vb;
+      long pos = r0 + r;
+      pos = pos < rend ? pos : rend - 1;
+      const long gr = p.row_idx ? p.row_idx[pos] : pos;
+      va[u] = *reinterpret_cast<const float4*>(A + gr * lda + ta * C::OT + q * 4);
+      vb[u] = *reinterpret_cast<const float4*>(B + gr * ldb + tb * C::OT + q * 4);
+    }
+#pragma unroll
+    for (int u = 0; u < ITER; ++u) {
+      const int c = tid + u * 256;
+      const int r = c / CH, q = c - r * CH;
+      float4 a = va[u], b = vb[u];
+      if (p.a_silu) { a.x = silu_f(a.x); a.y = silu_f(a.y); a.z = silu_f(a.z); a.w = silu_f(a.w); }
+      if (r0 + r >= rend) { a = make_float4(0.f, 0.f, 0.f, 0.f); b = a; }
+      *reinterpret_cast<float4*>(&sA[r * C::STRIDE + q * 4]) = a;
+      *reinterpret_cast<float4*>(&sB[r * C::STRIDE + q * 4]) = b;
     }
     __syncthreads();
     if (BF16) {
@@ -404,9 +459,9 @@ __global__ void __launch_bounds__(256) k_wgrad(WgradArgs p, int nsplit, int rows
 }
 
 int wgrad_splits(int64_t M) {
-  int64_t s = (M + 4095) / 4096;
+  int64_t s = (M + 255) / 256;   // about 256 rows per split: enough workgroups to fill the chip at N ~ 10^4..10^5
   if (s < 1) s = 1;
-  if (s > 192) s = 192;
+  if (s > 160) s = 160;
   return (int)s;
 }
 
@@ -453,35 +508,52 @@ int32_t launch_wgrad(hipStream_t st, int H, bool bf16, const WgradArgs& a) {
 // column sums
 // ---------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(256) k_colsum(ColsumArgs p, int H, int nsplit, int rows_per_split) {
-  __shared__ float sh[256];
+  // thread = (4-column chunk q, row phase ph); every phase walks its rows with four loads in flight
+  __shared__ float4 sh[256];
   const int tid = threadIdx.x;
-  const int c = tid % H, ph = tid / H, nph = 256 / H;
+  const int CH = H >> 2;
+  const int q = tid % CH, ph = tid / CH, nph = 256 / CH;
   const int split = blockIdx.x, grp = blockIdx.y;
   long gbeg = 0, gend = p.M;
   if (p.grp_ptr) { gbeg = p.grp_ptr[grp]; gend = p.grp_ptr[grp + 1]; }
   long rbeg = gbeg + (long)split * rows_per_split;
   long rend = rbeg + rows_per_split;
   if (rend > gend) rend = gend;
-  float s = 0.f;
-  for (long r = rbeg + ph; r < rend; r += nph) {
-    const long gr = p.row_idx ? p.row_idx[r] : r;
-    float x = p.X[gr * p.ldx + c];
-    if (p.f_silu) x = silu_f(x);
-    if (p.w) x *= p.w[gr];
-    s += x;
+  float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (long r0 = rbeg + ph; r0 < rend; r0 += 4 * nph) {
+    float4 xv[4];
+    float wv[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      long r = r0 + (long)u * nph;
+      r = r < rend ? r : rend - 1;
+      const long gr = p.row_idx ? p.row_idx[r] : r;
+      xv[u] = *reinterpret_cast<const float4*>(p.X + gr * p.ldx + q * 4);
+      wv[u] = p.w ? p.w[gr] : 1.f;
+      if (r0 + (long)u * nph >= rend) wv[u] = 0.f;
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      float4 x = xv[u];
+      if (p.f_silu) { x.x = silu_f(x.x); x.y = silu_f(x.y); x.z = silu_f(x.z); x.w = silu_f(x.w); }
+      s.x += wv[u] * x.x; s.y += wv[u] * x.y; s.z += wv[u] * x.z; s.w += wv[u] * x.w;
+    }
   }
   sh[tid] = s;
   __syncthreads();
   if (ph == 0) {
-    for (int k = 1; k < nph; ++k) s += sh[k * H + c];
-    p.partial[((long)grp * nsplit + split) * H + c] = s;
+    for (int k = 1; k < nph; ++k) {
+      const float4 t = sh[k * CH + q];
+      s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
+    }
+    *reinterpret_cast<float4*>(p.partial + ((long)grp * nsplit + split) * H + q * 4) = s;
   }
 }
 
 static int colsum_splits(int64_t M) {
-  int64_t s = (M + 1023) / 1024;
+  int64_t s = (M + 63) / 64;
   if (s < 1) s = 1;
-  if (s > 512) s = 512;
+  if (s > 1024) s = 1024;
   return (int)s;
 }
 

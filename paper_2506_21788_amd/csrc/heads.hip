@@ -32,29 +32,53 @@ __global__ void k_embed_fwd(int N, int H, const int32_t* __restrict__ Z, const f
   *reinterpret_cast<float4*>(h + i * H + q * 4) = *reinterpret_cast<const float4*>(emb + (long)z * H + q * 4);
 }
 
-// one block per table row z: fixed-order sum over the atoms with Z == z
+// block (z, chunk): fixed-order sum over the atoms of one chunk that have Z == z; chunks are then
+// summed in order by a second kernel
+constexpr int EMB_CHUNK = 2048;
+
 __global__ void __launch_bounds__(256)
-k_embed_bwd(int N, int H, const int32_t* __restrict__ Z, const float* __restrict__ g_h, float* __restrict__ g_emb) {
-  __shared__ float sh[256 * 4];
-  const int z = blockIdx.x;
+k_embed_bwd_part(int N, int H, const int32_t* __restrict__ Z, const float* __restrict__ g_h,
+                 float* __restrict__ part /*[nchunk][ZMAX+1][H]*/) {
+  __shared__ float4 sh[256];
+  const int z = blockIdx.x, chunk = blockIdx.y;
   const int CH = H >> 2;
   const int q = threadIdx.x % CH, ph = threadIdx.x / CH, nph = 256 / CH;
+  const int lo = chunk * EMB_CHUNK;
+  const int hi = lo + EMB_CHUNK < N ? lo + EMB_CHUNK : N;
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-  for (int i = ph; i < N; i += nph) {
-    if (Z[i] == z) {
-      const float4 v = *reinterpret_cast<const float4*>(g_h + (size_t)i * H + q * 4);
-      acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+  for (int i0 = lo + ph; i0 < hi; i0 += 8 * nph) {
+    int zz[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int i = i0 + u * nph;
+      zz[u] = i < hi ? Z[i] : -1;
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      if (zz[u] == z) {
+        const float4 v = *reinterpret_cast<const float4*>(g_h + (size_t)(i0 + u * nph) * H + q * 4);
+        acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+      }
     }
   }
-  reinterpret_cast<float4*>(sh)[threadIdx.x] = acc;
+  sh[threadIdx.x] = acc;
   __syncthreads();
   if (ph == 0) {
     for (int k = 1; k < nph; ++k) {
-      const float4 v = reinterpret_cast<float4*>(sh)[k * CH + q];
+      const float4 v = sh[k * CH + q];
       acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
     }
-    *reinterpret_cast<float4*>(g_emb + (size_t)z * H + q * 4) = acc;
+    *reinterpret_cast<float4*>(part + ((size_t)chunk * (HGNN_ZMAX + 1) + z) * H + q * 4) = acc;
   }
+}
+
+__global__ void k_embed_bwd_sum(int nchunk, int H, const float* __restrict__ part, float* __restrict__ g_emb) {
+  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  const int total = (HGNN_ZMAX + 1) * H;
+  if (idx >= total) return;
+  float s = 0.f;
+  for (int c = 0; c < nchunk; ++c) s += part[(size_t)c * total + idx];
+  g_emb[idx] = s;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -345,13 +369,30 @@ extern "C" int32_t hgnn_embed_fwd(void* stream, int32_t N, int32_t H, const int3
   return HGNN_OK;
 }
 
-extern "C" int32_t hgnn_embed_bwd(void* stream, int32_t N, int32_t H, const int32_t* Z, const float* g_h, float* g_emb) {
+extern "C" int32_t hgnn_embed_bwd_workspace_bytes(int32_t N, int32_t H, size_t* ws_bytes_host) {
+  HGNN_REQUIRE(N >= 0 && valid_H(H), HGNN_ERR_BAD_SHAPE, "embed_bwd: bad N or H");
+  HGNN_REQUIRE(ws_bytes_host, HGNN_ERR_NULLPTR, "null size pointer");
+  const size_t nchunk = ((size_t)N + EMB_CHUNK - 1) / EMB_CHUNK;
+  *ws_bytes_host = align_up((nchunk > 0 ? nchunk : 1) * (HGNN_ZMAX + 1) * H * sizeof(float));
+  return HGNN_OK;
+}
+
+extern "C" int32_t hgnn_embed_bwd(void* stream, int32_t N, int32_t H, const int32_t* Z, const float* g_h, float* g_emb,
+                                  void* ws, size_t ws_bytes) {
   hipStream_t st = static_cast<hipStream_t>(stream);
   HGNN_REQUIRE(N >= 0 && valid_H(H), HGNN_ERR_BAD_SHAPE, "embed_bwd: bad N or H");
-  HGNN_REQUIRE(g_emb && (N == 0 || (Z && g_h)), HGNN_ERR_NULLPTR, "embed_bwd: null pointer");
+  HGNN_REQUIRE(g_emb && ws && (N == 0 || (Z && g_h)), HGNN_ERR_NULLPTR, "embed_bwd: null pointer");
+  size_t need = 0;
+  HGNN_TRY(hgnn_embed_bwd_workspace_bytes(N, H, &need));
+  HGNN_REQUIRE(ws_bytes >= need, HGNN_ERR_WORKSPACE_TOO_SMALL, "embed_bwd workspace: need %zu bytes, got %zu", need, ws_bytes);
+  const int nchunk = (N + EMB_CHUNK - 1) / EMB_CHUNK;
   ProfScope ps(PT_EMBED, st);
-  k_embed_bwd<<<HGNN_ZMAX + 1, 256, 0, st>>>(N, H, Z, g_h, g_emb);
-  HGNN_LAUNCH_CHECK("k_embed_bwd");
+  if (nchunk > 0) {
+    k_embed_bwd_part<<<dim3(HGNN_ZMAX + 1, nchunk), 256, 0, st>>>(N, H, Z, g_h, static_cast<float*>(ws));
+    HGNN_LAUNCH_CHECK("k_embed_bwd_part");
+  }
+  k_embed_bwd_sum<<<((HGNN_ZMAX + 1) * H + 255) / 256, 256, 0, st>>>(nchunk, H, static_cast<const float*>(ws), g_emb);
+  HGNN_LAUNCH_CHECK("k_embed_bwd_sum");
   return HGNN_OK;
 }
 

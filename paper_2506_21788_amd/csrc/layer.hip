@@ -30,7 +30,7 @@ struct LayerOff {  // element offsets into the flat weight buffer
 };
 
 struct LayerSaved {
-  float* PQ;    // [N,2H]  P = h W1a + b1 | Q = h W1b
+  float* PQ;    // [N,2H] fp32  P = h W1a + b1 | Q = h W1b   (or the same as bf16 pairs, [N,H] words)
   void* z2_vm;  // [E32,H] z2, v-major fragment order (bf16 or fp32)
   void* a1_pk;  // [E32,H] silu(z1), operand-packed fragment order (bf16 or fp32)
   float* M;     // [N,H]
@@ -58,6 +58,7 @@ struct LayerWs {
   float* cvec;     // [E]
   float* g_z3;     // [N,H]
   float* g_hM;     // [N,2H]
+  unsigned* gM_pk; // [N,H/2] words: g_M as bf16 pairs (only when the fused kernels gather pairs)
   float* g_PQ;     // [N,2H]
   float* partial;  // split-K / column-sum partials
   size_t bytes;
@@ -72,6 +73,7 @@ static LayerWs carve_ws(void* p, int N, int64_t E, int H, bool bf16) {
   w.cvec = c.take<float>((size_t)E + 4);
   w.g_z3 = c.take<float>((size_t)N * H);
   w.g_hM = c.take<float>((size_t)N * 2 * H);
+  w.gM_pk = c.take<unsigned>((size_t)N * (H / 2));
   w.g_PQ = c.take<float>((size_t)N * 2 * H);
   size_t pf = wgrad_partial_floats(H, N, 2, 1);
   const size_t cands[3] = {colsum_partial_floats(H, N, 1), wgrad_frag_partial_floats(H), edge_bwd_colpart_floats(H)};
@@ -143,6 +145,10 @@ extern "C" int32_t hgnn_mp_layer_fwd(void* stream, int32_t N, int64_t E, int32_t
     g.M = N;
     g.bias = W + o.b1; g.bias_cb_mask = 1;
     g.C = s.PQ; g.ldc = 2 * H;
+    if (edge_pairs(H, bf16)) {
+      g.Cpair = reinterpret_cast<unsigned*>(s.PQ); g.ldpair = H; g.pair_cb_mask = 3;
+      g.pair_off[0] = 0; g.pair_off[1] = H / 2;
+    }
     HGNN_TRY(launch_gemm(st, H, bf16, g));
   }
   {  // per edge: a1 = silu(P[dst] + Q[col] + d2*w1d), z2 = a1 W2 + b2   (one fused kernel)
@@ -240,6 +246,9 @@ extern "C" int32_t hgnn_mp_layer_bwd(void* stream, int32_t N, int64_t E, int32_t
     g.B = w.packed; g.blk[0][0] = 1; g.blk[0][1] = 2; g.ncb = 2;
     g.M = N;
     g.C = w.g_hM; g.ldc = 2 * H;
+    if (edge_pairs(H, bf16)) {   // the g_M half goes out as bf16 pairs for the fused edge kernel
+      g.Cpair = w.gM_pk; g.ldpair = H / 2; g.pair_cb_mask = 2; g.pair_off[1] = 0;
+    }
     HGNN_TRY(launch_gemm(st, H, bf16, g));
   }
   {  // gW3 = [h ; M]^T g_z3 ; gb3
@@ -262,7 +271,8 @@ extern "C" int32_t hgnn_mp_layer_bwd(void* stream, int32_t N, int64_t E, int32_t
     e.PQ = s.PQ; e.w1d = W + o.W1 + 2 * HH;
     e.W2Tp = static_cast<const char*>(w.packed) + 3 * packed_block_bytes(H, bf16);
     e.z2_vm = s.z2_vm;
-    e.gM = w.g_hM + H; e.ldgM = 2 * H;
+    if (edge_pairs(H, bf16)) { e.gM = w.gM_pk; e.ldgM = H / 2; }
+    else { e.gM = w.g_hM + H; e.ldgM = 2 * H; }
     e.cvec = w.cvec; e.wx = W + o.wx; e.alpha = alpha;
     e.gz2_pk = w.gz2_pk; e.gz1_vm = w.gz1_vm;
     e.colpart = w.partial;

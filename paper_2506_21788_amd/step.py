@@ -97,7 +97,7 @@ class HotPath:
         f32 = dict(dtype=torch.float32, device="cuda")
         ws_b, saved_b = B.mp_layer_workspace_bytes(N, E, H, self.dtype)
         hws_b, hsaved_b = B.multihead_decode_workspace_bytes(N, G, H, self.Hh, S, self.dtype)
-        self.ws = _bytes(max(ws_b, hws_b))
+        self.ws = _bytes(max(ws_b, hws_b, B.embed_bwd_workspace_bytes(N, H)))
         self.saved = [_bytes(saved_b) for _ in range(L)]
         self.hsaved = _bytes(hsaved_b)
         self.h = [torch.empty((N, H), **f32) for _ in range(L + 1)]
@@ -136,7 +136,7 @@ class HotPath:
                            g.permT, self.h[l], self.W[l], self.saved[l], self.g_h[cur], self.g_v[cur],
                            self.g_h[1 - cur], self.g_v[1 - cur], self.gW[l], self.ws)
             cur = 1 - cur
-        B.embed_bwd(N, H, self.Z, self.g_h[cur], self.g_emb)
+        B.embed_bwd(N, H, self.Z, self.g_h[cur], self.g_emb, self.ws)
         self.g_h0, self.g_v0 = self.g_h[cur], self.g_v[cur]
 
     def step(self, g_energy, g_force, with_graph=True):
