@@ -56,7 +56,7 @@ struct EdgeBwdArgs {
   const float* wx;     // [H]
   float alpha;
   void* gz2_pk;        // out: g_z2, operand-packed
-  float* gz1_vm;       // out: g_z1, v-major fp32
+  void* gz1_vm;        // out: g_z1, v-major (bf16 or fp32, like the operands)
   float* colpart;      // scratch: [splits][3][H] partial column sums (b2, wx, w1d)
   float* g_b2;         // out [H]
   float* g_wx;         // out [H]
@@ -74,8 +74,9 @@ size_t wgrad_frag_partial_floats(int H);
 int32_t launch_wgrad_frag(hipStream_t st, int H, bool bf16, int64_t E, const void* a1_pk, const void* gz2_pk,
                           float* partial, float* gW2);
 
-// out[i, 0..H) (row pitch ldo) = sum over t in ptr[i]:ptr[i+1] of X[perm ? perm[t] : t, :], X v-major fp32
-int32_t launch_segsum_vm(hipStream_t st, int H, int N, const int32_t* ptr, const int32_t* perm, const float* X_vm,
-                         float* out, int ldo, int tag);
+// out[i, 0..H) (row pitch ldo) = sum over t in ptr[i]:ptr[i+1] of X[perm ? perm[t] : t, :], X v-major (bf16 or
+// fp32), accumulated in fp32
+int32_t launch_segsum_vm(hipStream_t st, int H, bool bf16, int N, const int32_t* ptr, const int32_t* perm,
+                         const void* X_vm, float* out, int ldo, int tag);
 
 }  // namespace hgnn

@@ -500,9 +500,9 @@ int32_t launch_seg_fwd_vm(hipStream_t st, int H, bool bf16, int N, const int32_t
   return HGNN_OK;
 }
 
-template <int H>
+template <int H, bool BF16>
 __global__ void __launch_bounds__(256)
-k_segsum_vm(int N, const int32_t* __restrict__ ptr, const int32_t* __restrict__ perm, const float* __restrict__ X,
+k_segsum_vm(int N, const int32_t* __restrict__ ptr, const int32_t* __restrict__ perm, const void* __restrict__ X,
             float* __restrict__ out, int ldo) {
   constexpr int NCB = H / 32;
   constexpr int NC = NCB / 2;
@@ -517,23 +517,28 @@ k_segsum_vm(int N, const int32_t* __restrict__ ptr, const int32_t* __restrict__ 
   for (int t = t0; t < t1; ++t) {
     const size_t e = perm ? (size_t)perm[t] : (size_t)t;
 #pragma unroll
-    for (int c = 0; c < NC; ++c) acc[c] += X[vm_index<NCB>(e, 2 * c + hp, x)];
+    for (int c = 0; c < NC; ++c) {
+      const size_t idx = vm_index<NCB>(e, 2 * c + hp, x);
+      acc[c] += BF16 ? bf_bits_to_f(reinterpret_cast<const unsigned short*>(X)[idx]) : reinterpret_cast<const float*>(X)[idx];
+    }
   }
 #pragma unroll
   for (int c = 0; c < NC; ++c) out[(size_t)i * ldo + (2 * c + hp) * 32 + x] = acc[c];
 }
 
-int32_t launch_segsum_vm(hipStream_t st, int H, int N, const int32_t* ptr, const int32_t* perm, const float* X_vm,
-                         float* out, int ldo, int tag) {
+int32_t launch_segsum_vm(hipStream_t st, int H, bool bf16, int N, const int32_t* ptr, const int32_t* perm,
+                         const void* X_vm, float* out, int ldo, int tag) {
   if (N <= 0) return HGNN_OK;
   const unsigned grid = (unsigned)(((int64_t)N * 64 + 255) / 256);
   ProfScope ps(tag, st);
+#define HGNN_SEGS(HH, BB) k_segsum_vm<HH, BB><<<grid, 256, 0, st>>>(N, ptr, perm, X_vm, out, ldo)
   switch (H) {
-    case 64: k_segsum_vm<64><<<grid, 256, 0, st>>>(N, ptr, perm, X_vm, out, ldo); break;
-    case 128: k_segsum_vm<128><<<grid, 256, 0, st>>>(N, ptr, perm, X_vm, out, ldo); break;
-    case 256: k_segsum_vm<256><<<grid, 256, 0, st>>>(N, ptr, perm, X_vm, out, ldo); break;
+    case 64: if (bf16) HGNN_SEGS(64, true); else HGNN_SEGS(64, false); break;
+    case 128: if (bf16) HGNN_SEGS(128, true); else HGNN_SEGS(128, false); break;
+    case 256: if (bf16) HGNN_SEGS(256, true); else HGNN_SEGS(256, false); break;
     default: return set_error(HGNN_ERR_BAD_SHAPE, "H must be 64, 128 or 256");
   }
+#undef HGNN_SEGS
   HGNN_LAUNCH_CHECK("k_segsum_vm");
   return HGNN_OK;
 }
@@ -667,11 +672,25 @@ __global__ void __launch_bounds__(256) k_edge_bwd(EdgeBwdArgs p, int ntiles) {
 #pragma unroll
         for (int j = 0; j < C::CB; ++j) {
           const size_t base = (((size_t)eb * C::NCB + (wc * C::CB + j)) * 16 + 8 * vh) * 64 + lane;
+          float gv[8];
 #pragma unroll
           for (int u = 0; u < 8; ++u) {
             const float gz1 = acc[i][j][8 * vh + u] * dsilu_f(z[j][u]);   // rows beyond E have acc == 0
-            __builtin_nontemporal_store(gz1, p.gz1_vm + base + u * 64);
+            gv[u] = gz1;
             sw1[j] += dd[u] * gz1;
+          }
+          if constexpr (BF16) {
+            unsigned short* o = reinterpret_cast<unsigned short*>(p.gz1_vm) + base;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+              const unsigned pk = pack_bf16x2(gv[2 * t], gv[2 * t + 1]);
+              __builtin_nontemporal_store((unsigned short)(pk & 0xffffu), o + (2 * t) * 64);
+              __builtin_nontemporal_store((unsigned short)(pk >> 16), o + (2 * t + 1) * 64);
+            }
+          } else {
+            float* o = reinterpret_cast<float*>(p.gz1_vm) + base;
+#pragma unroll
+            for (int u = 0; u < 8; ++u) __builtin_nontemporal_store(gv[u], o + u * 64);
           }
         }
       }
@@ -749,49 +768,63 @@ k_wgrad_frag(int64_t nblk32, int blocks_per_wg, const void* __restrict__ a1_pk, 
   int64_t eb0 = (int64_t)blockIdx.x * blocks_per_wg;
   int64_t eb1 = eb0 + blocks_per_wg;
   if (eb1 > nblk32) eb1 = nblk32;
-  if (BF16) {
+  // one chunk = one matrix-core operand per block column: 16 edges (bf16) or 4 edges (fp32, four instructions);
+  // chunks are double buffered in registers so that the loads of the next one overlap the products of this one
+  constexpr int CPB = BF16 ? 2 : 4;   // chunks per 32-edge block
+  const int64_t nchunk = (eb1 > eb0) ? (eb1 - eb0) * CPB : 0;
+#define HGNN_WG_LOAD(c, a, b)                                                                          \
+  {                                                                                                    \
+    const size_t eb_ = (size_t)(eb0 + (c) / CPB);                                                      \
+    const int sub_ = (int)((c) % CPB);                                                                 \
+    _Pragma("unroll") for (int i = 0; i < NBW; ++i) {                                                  \
+      a[i] = __builtin_nontemporal_load(A + ((eb_ * NCB + wa * NBW + i) * CPB + sub_) * 64 + lane);    \
+      b[i] = __builtin_nontemporal_load(B + ((eb_ * NCB + wb * NBW + i) * CPB + sub_) * 64 + lane);    \
+    }                                                                                                  \
+  }
+  if constexpr (BF16) {
     const bf16x8_t* __restrict__ A = reinterpret_cast<const bf16x8_t*>(a1_pk);
     const bf16x8_t* __restrict__ B = reinterpret_cast<const bf16x8_t*>(gz2_pk);
-    for (int64_t eb = eb0; eb < eb1; ++eb) {
-#pragma unroll
-      for (int vh = 0; vh < 2; ++vh) {
-        bf16x8_t a[NBW], b[NBW];
-#pragma unroll
-        for (int i = 0; i < NBW; ++i) {
-          a[i] = A[(((size_t)eb * NCB + wa * NBW + i) * 2 + vh) * 64 + lane];
-          b[i] = B[(((size_t)eb * NCB + wb * NBW + i) * 2 + vh) * 64 + lane];
-        }
-#pragma unroll
-        for (int i = 0; i < NBW; ++i)
-#pragma unroll
-          for (int j = 0; j < NBW; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+    bf16x8_t a0[NBW], b0[NBW], a1[NBW], b1[NBW];
+#define HGNN_WG_MMA(a, b)                                                                              \
+  _Pragma("unroll") for (int i = 0; i < NBW; ++i) _Pragma("unroll") for (int j = 0; j < NBW; ++j)      \
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+    // nchunk is even; the prefetch past the end is clamped to the last chunk (loaded again, never used)
+    if (nchunk > 0) {
+      HGNN_WG_LOAD(0, a0, b0)
+      for (int64_t c = 0; c < nchunk; c += 2) {
+        HGNN_WG_LOAD(c + 1, a1, b1)
+        HGNN_WG_MMA(a0, b0)
+        const int64_t cn = c + 2 < nchunk ? c + 2 : nchunk - 1;
+        HGNN_WG_LOAD(cn, a0, b0)
+        HGNN_WG_MMA(a1, b1)
       }
     }
+#undef HGNN_WG_MMA
   } else {
-    const float4* __restrict__ A = reinterpret_cast<const float4*>(a1_pk);
-    const float4* __restrict__ B = reinterpret_cast<const float4*>(gz2_pk);
-    for (int64_t eb = eb0; eb < eb1; ++eb) {
-#pragma unroll
-      for (int vq = 0; vq < 4; ++vq) {
-        float4 a[NBW], b[NBW];
-#pragma unroll
-        for (int i = 0; i < NBW; ++i) {
-          a[i] = A[(((size_t)eb * NCB + wa * NBW + i) * 4 + vq) * 64 + lane];
-          b[i] = B[(((size_t)eb * NCB + wb * NBW + i) * 4 + vq) * 64 + lane];
-        }
-#pragma unroll
-        for (int i = 0; i < NBW; ++i)
-#pragma unroll
-          for (int j = 0; j < NBW; ++j) {
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].x, b[j].x, acc[i][j], 0, 0, 0);
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].y, b[j].y, acc[i][j], 0, 0, 0);
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].z, b[j].z, acc[i][j], 0, 0, 0);
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].w, b[j].w, acc[i][j], 0, 0, 0);
-          }
+    const f32x4_t* __restrict__ A = reinterpret_cast<const f32x4_t*>(a1_pk);
+    const f32x4_t* __restrict__ B = reinterpret_cast<const f32x4_t*>(gz2_pk);
+    f32x4_t a0[NBW], b0[NBW], a1[NBW], b1[NBW];
+#define HGNN_WG_MMA(a, b)                                                                              \
+  _Pragma("unroll") for (int i = 0; i < NBW; ++i) _Pragma("unroll") for (int j = 0; j < NBW; ++j) {    \
+    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i][0], b[j][0], acc[i][j], 0, 0, 0);            \
+    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i][1], b[j][1], acc[i][j], 0, 0, 0);            \
+    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i][2], b[j][2], acc[i][j], 0, 0, 0);            \
+    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i][3], b[j][3], acc[i][j], 0, 0, 0);            \
+  }
+    // nchunk is even; the prefetch past the end is clamped to the last chunk (loaded again, never used)
+    if (nchunk > 0) {
+      HGNN_WG_LOAD(0, a0, b0)
+      for (int64_t c = 0; c < nchunk; c += 2) {
+        HGNN_WG_LOAD(c + 1, a1, b1)
+        HGNN_WG_MMA(a0, b0)
+        const int64_t cn = c + 2 < nchunk ? c + 2 : nchunk - 1;
+        HGNN_WG_LOAD(cn, a0, b0)
+        HGNN_WG_MMA(a1, b1)
       }
     }
+#undef HGNN_WG_MMA
   }
+#undef HGNN_WG_LOAD
   float* out = partial + (size_t)blockIdx.x * H * H;
 #pragma unroll
   for (int i = 0; i < NBW; ++i)

@@ -228,26 +228,36 @@ __global__ void __launch_bounds__(256) k_gemm(GemmArgs p) {
     }
   }
 #pragma unroll
-  for (int j = 0; j < C::CB; ++j) {
-    const int col = wc * C::WCOLS + j * 32 + (lane & 31);
-    const int gcol = cb * H + col;
-    const float bv = use_bias ? p.bias[grp * p.grp_bias_stride + col] : 0.f;
+  for (int i = 0; i < C::RB; ++i) {
+    // the 16 rows of this lane in row block i (clamped to the last valid row so that every load below is
+    // unconditional and all of them can be in flight together)
+    long grow[16];
 #pragma unroll
-    for (int i = 0; i < C::RB; ++i) {
+    for (int v = 0; v < 16; ++v) {
+      const int r = wr * C::WROWS + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+      int pos = rbeg + r;
+      pos = pos < rend ? pos : rend - 1;
+      grow[v] = p.row_idx ? p.row_idx[pos] : pos;
+    }
+#pragma unroll
+    for (int j = 0; j < C::CB; ++j) {
+      const int col = wc * C::WCOLS + j * 32 + (lane & 31);
+      const int gcol = cb * H + col;
+      const float bv = use_bias ? p.bias[grp * p.grp_bias_stride + col] : 0.f;
+      float mv[16], a1[16], a2[16];
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        mv[v] = p.mul ? p.mul[grow[v] * p.ldmul + gcol] : 1.f;
+        a1[v] = p.add1 ? p.add1[grow[v] * p.ldadd1 + gcol] : 0.f;
+        a2[v] = p.add2 ? p.add2[grow[v] * p.ldadd2 + gcol] : 0.f;
+      }
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int r = wr * C::WROWS + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-        const int pos = rbeg + r;
-        if (pos < rend) {
-          const long gr = p.row_idx ? p.row_idx[pos] : pos;
+        if (rbeg + r < rend) {
           float x = acc[i][j][v] + bv;
-          if (p.mul) {
-            const float mval = p.mul[gr * p.ldmul + gcol];
-            x *= p.mul_is_z ? dsilu_f(mval) : mval;
-          }
-          if (p.add1) x += p.add1[gr * p.ldadd1 + gcol];
-          if (p.add2) x += p.add2[gr * p.ldadd2 + gcol];
-          p.C[gr * p.ldc + gcol] = x;
+          if (p.mul) x *= p.mul_is_z ? dsilu_f(mv[v]) : mv[v];
+          p.C[grow[v] * p.ldc + gcol] = x + a1[v] + a2[v];
         }
       }
     }

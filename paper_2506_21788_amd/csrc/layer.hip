@@ -54,7 +54,7 @@ static LayerSaved carve_saved(void* p, int N, int64_t E, int H, bool bf16) {
 struct LayerWs {
   void* packed;    // 6 blocks
   void* gz2_pk;    // [E32,H] operand-packed
-  float* gz1_vm;   // [E32,H] v-major fp32
+  void* gz1_vm;    // [E32,H] v-major (bf16 or fp32)
   float* cvec;     // [E]
   float* g_z3;     // [N,H]
   float* g_hM;     // [N,2H]
@@ -69,7 +69,7 @@ static LayerWs carve_ws(void* p, int N, int64_t E, int H, bool bf16) {
   LayerWs w;
   w.packed = c.take<char>(6 * packed_block_bytes(H, bf16));
   w.gz2_pk = c.take<char>(frag_rows(E) * H * (bf16 ? 2 : 4));
-  w.gz1_vm = c.take<float>(frag_rows(E) * H);
+  w.gz1_vm = c.take<char>(frag_rows(E) * H * (bf16 ? 2 : 4));
   w.cvec = c.take<float>((size_t)E + 4);
   w.g_z3 = c.take<float>((size_t)N * H);
   w.g_hM = c.take<float>((size_t)N * 2 * H);
@@ -280,8 +280,8 @@ extern "C" int32_t hgnn_mp_layer_bwd(void* stream, int32_t N, int64_t E, int32_t
     HGNN_TRY(launch_edge_bwd(st, H, bf16, e));
   }
   HGNN_TRY(launch_wgrad_frag(st, H, bf16, E, s.a1_pk, w.gz2_pk, w.partial, gW + o.W2));
-  HGNN_TRY(launch_segsum_vm(st, H, N, row_ptr, nullptr, w.gz1_vm, w.g_PQ, 2 * H, PT_SEGSUM_DST));     // g_P
-  HGNN_TRY(launch_segsum_vm(st, H, N, colT_ptr, permT, w.gz1_vm, w.g_PQ + H, 2 * H, PT_SEGSUM_SRC));  // g_Q
+  HGNN_TRY(launch_segsum_vm(st, H, bf16, N, row_ptr, nullptr, w.gz1_vm, w.g_PQ, 2 * H, PT_SEGSUM_DST));     // g_P
+  HGNN_TRY(launch_segsum_vm(st, H, bf16, N, colT_ptr, permT, w.gz1_vm, w.g_PQ + H, 2 * H, PT_SEGSUM_SRC));  // g_Q
   {
     ColsumArgs c2;  // gb1 = sum_i g_P_i
     c2.X = w.g_PQ; c2.ldx = 2 * H; c2.M = N; c2.dest = gW + o.b1; c2.partial = w.partial;
