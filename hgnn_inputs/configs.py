@@ -58,7 +58,7 @@ def _gen_cfg3(rng) -> Batch:
     return concat_graphs(graphs)
 
 
-def _gen_cfg4(rng, n_target=40000, crystal_density_cap=0.12) -> Batch:
+def _gen_cfg4(rng, n_target=40000, crystal_density_cap=0.085) -> Batch:
     graphs, src = [], []
     total = 0
     while total < n_target:

@@ -361,26 +361,33 @@ __global__ void __launch_bounds__(256, 2) k_edge_fwd(EdgeFwdArgs p, int ntiles) 
     else tile_mma<H, BF16>(smem, p.W2p, wr, wc, lane, acc);
     if (tid < 3 * C::TM) sc[(buf ^ 1) * 3 * C::TM + tid] = nxt;
     __syncthreads();
-    // ---- z2 = acc + b2, stored v-major
+    // ---- z2 = acc + b2, stored v-major (as bf16 pairs of this lane's two column blocks when PAIRS)
 #pragma unroll
     for (int i = 0; i < C::RB; ++i) {
       const int64_t eb = (int64_t)tile * (C::TM / 32) + wr * C::RB + i;
       if (eb * 32 >= E) continue;
+      if constexpr (PAIRS) {
+        unsigned* o = reinterpret_cast<unsigned*>(p.z2_vm) + (((size_t)eb * (C::NCB / 2) + wc) * 16) * 64 + lane;
 #pragma unroll
-      for (int j = 0; j < C::CB; ++j) {
-        const size_t base = (((size_t)eb * C::NCB + (wc * C::CB + j)) * 16) * 64 + lane;
-        if (BF16) {
-          unsigned short* o = reinterpret_cast<unsigned short*>(p.z2_vm) + base;
+        for (int v = 0; v < 16; ++v)
+          __builtin_nontemporal_store(pack_bf16x2(acc[i][0][v] + b2[0], acc[i][1][v] + b2[1]), o + v * 64);
+      } else {
 #pragma unroll
-          for (int t = 0; t < 8; ++t) {
-            const unsigned pk = pack_bf16x2(acc[i][j][2 * t] + b2[j], acc[i][j][2 * t + 1] + b2[j]);
-            __builtin_nontemporal_store((unsigned short)(pk & 0xffffu), o + (2 * t) * 64);
-            __builtin_nontemporal_store((unsigned short)(pk >> 16), o + (2 * t + 1) * 64);
+        for (int j = 0; j < C::CB; ++j) {
+          const size_t base = (((size_t)eb * C::NCB + (wc * C::CB + j)) * 16) * 64 + lane;
+          if (BF16) {
+            unsigned short* o = reinterpret_cast<unsigned short*>(p.z2_vm) + base;
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+              const unsigned pk = pack_bf16x2(acc[i][j][2 * t] + b2[j], acc[i][j][2 * t + 1] + b2[j]);
+              __builtin_nontemporal_store((unsigned short)(pk & 0xffffu), o + (2 * t) * 64);
+              __builtin_nontemporal_store((unsigned short)(pk >> 16), o + (2 * t + 1) * 64);
+            }
+          } else {
+            float* o = reinterpret_cast<float*>(p.z2_vm) + base;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) __builtin_nontemporal_store(acc[i][j][v] + b2[j], o + v * 64);
           }
-        } else {
-          float* o = reinterpret_cast<float*>(p.z2_vm) + base;
-#pragma unroll
-          for (int v = 0; v < 16; ++v) __builtin_nontemporal_store(acc[i][j][v] + b2[j], o + v * 64);
         }
       }
     }
@@ -433,29 +440,52 @@ __device__ __forceinline__ size_t vm_index(size_t e, int cb, int x) {
   return (((e >> 5) * NCB + cb) * 16 + v) * 64 + gg * 32 + x;
 }
 
+// Two columns of edge e for one lane of a segment kernel. Lane (hp = lane>>5, x = lane&31), pass c:
+//   PAIRS: one 32-bit word = columns (2c+hp)*64 + x and (2c+hp)*64 + 32 + x      (passes: NCB/4)
+//   else:  column block 2c+hp, single column (2c+hp)*32 + x; second value unused  (passes: NCB/2)
+template <int H, bool BF16, bool PAIRS>
+struct SegCols {
+  static constexpr int NCB = H / 32;
+  static constexpr int NPASS = PAIRS ? NCB / 4 : NCB / 2;
+  static constexpr int PER = PAIRS ? 2 : 1;
+  __device__ static __forceinline__ void fetch(const void* __restrict__ X, size_t e, int c, int hp, int x, float* out) {
+    if constexpr (PAIRS) {
+      const unsigned w = reinterpret_cast<const unsigned*>(X)[vm_index<NCB / 2>(e, 2 * c + hp, x)];
+      out[0] = __uint_as_float(w << 16);
+      out[1] = __uint_as_float(w & 0xffff0000u);
+    } else {
+      const size_t idx = vm_index<NCB>(e, 2 * c + hp, x);
+      out[0] = BF16 ? bf_bits_to_f(reinterpret_cast<const unsigned short*>(X)[idx]) : reinterpret_cast<const float*>(X)[idx];
+    }
+  }
+  __device__ static __forceinline__ int column(int c, int hp, int x, int k) {
+    return PAIRS ? (2 * c + hp) * 64 + 32 * k + x : (2 * c + hp) * 32 + x;
+  }
+};
+
 template <int H, bool BF16>
 __global__ void __launch_bounds__(256)
 k_seg_fwd_vm(int N, const int32_t* __restrict__ row_ptr, const void* __restrict__ z2_vm,
              const float* __restrict__ rvec, const float* __restrict__ wx, float alpha,
              const float* __restrict__ v_in, float* __restrict__ M, float* __restrict__ v_out) {
-  constexpr int NCB = H / 32;
-  constexpr int NC = NCB / 2;  // column blocks per lane half
+  using S = SegCols<H, BF16, BF16 && H == 256>;
+  constexpr int NV = S::NPASS * S::PER;
   const int i = __builtin_amdgcn_readfirstlane((int)(((size_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6));
   const int lane = threadIdx.x & 63;
   if (i >= N) return;
   const int hp = lane >> 5, x = lane & 31;
   const int e0 = row_ptr[i], e1 = row_ptr[i + 1];
-  float acc[NC], tx[NC], ty[NC], tz[NC];
+  float acc[NV], tx[NV], ty[NV], tz[NV];
 #pragma unroll
-  for (int c = 0; c < NC; ++c) acc[c] = tx[c] = ty[c] = tz[c] = 0.f;
+  for (int c = 0; c < NV; ++c) acc[c] = tx[c] = ty[c] = tz[c] = 0.f;
   for (int e = e0; e < e1; ++e) {
     const float rx = rvec[3 * (size_t)e], ry = rvec[3 * (size_t)e + 1], rz = rvec[3 * (size_t)e + 2];
+    float z[NV];
 #pragma unroll
-    for (int c = 0; c < NC; ++c) {
-      const size_t idx = vm_index<NCB>((size_t)e, 2 * c + hp, x);
-      const float z = BF16 ? bf_bits_to_f(reinterpret_cast<const unsigned short*>(z2_vm)[idx])
-                           : reinterpret_cast<const float*>(z2_vm)[idx];
-      const float m = silu_f(z);
+    for (int c = 0; c < S::NPASS; ++c) S::fetch(z2_vm, (size_t)e, c, hp, x, &z[c * S::PER]);
+#pragma unroll
+    for (int c = 0; c < NV; ++c) {
+      const float m = silu_f(z[c]);
       acc[c] += m;
       tx[c] += m * rx;
       ty[c] += m * ry;
@@ -464,14 +494,16 @@ k_seg_fwd_vm(int N, const int32_t* __restrict__ row_ptr, const void* __restrict_
   }
   float sx = 0.f, sy = 0.f, sz = 0.f;
 #pragma unroll
-  for (int c = 0; c < NC; ++c) {
-    const int n = (2 * c + hp) * 32 + x;
-    const float w = wx[n];
-    M[(size_t)i * H + n] = alpha * acc[c];
-    sx += w * tx[c];
-    sy += w * ty[c];
-    sz += w * tz[c];
-  }
+  for (int c = 0; c < S::NPASS; ++c)
+#pragma unroll
+    for (int k = 0; k < S::PER; ++k) {
+      const int n = S::column(c, hp, x, k);
+      const float w = wx[n];
+      M[(size_t)i * H + n] = alpha * acc[c * S::PER + k];
+      sx += w * tx[c * S::PER + k];
+      sy += w * ty[c * S::PER + k];
+      sz += w * tz[c * S::PER + k];
+    }
   sx = wave_sum64(sx);
   sy = wave_sum64(sy);
   sz = wave_sum64(sz);
@@ -504,26 +536,41 @@ template <int H, bool BF16>
 __global__ void __launch_bounds__(256)
 k_segsum_vm(int N, const int32_t* __restrict__ ptr, const int32_t* __restrict__ perm, const void* __restrict__ X,
             float* __restrict__ out, int ldo) {
-  constexpr int NCB = H / 32;
-  constexpr int NC = NCB / 2;
+  using S = SegCols<H, BF16, BF16 && H == 256>;
+  constexpr int NV = S::NPASS * S::PER;
   const int i = __builtin_amdgcn_readfirstlane((int)(((size_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6));
   const int lane = threadIdx.x & 63;
   if (i >= N) return;
   const int hp = lane >> 5, x = lane & 31;
   const int t0 = ptr[i], t1 = ptr[i + 1];
-  float acc[NC];
+  float acc[NV];
 #pragma unroll
-  for (int c = 0; c < NC; ++c) acc[c] = 0.f;
-  for (int t = t0; t < t1; ++t) {
-    const size_t e = perm ? (size_t)perm[t] : (size_t)t;
+  for (int c = 0; c < NV; ++c) acc[c] = 0.f;
+  int t = t0;
+  for (; t + 2 <= t1; t += 2) {   // two edges per trip: their loads are independent
+    const size_t ea = perm ? (size_t)perm[t] : (size_t)t;
+    const size_t eb = perm ? (size_t)perm[t + 1] : (size_t)(t + 1);
+    float va[NV], vb[NV];
 #pragma unroll
-    for (int c = 0; c < NC; ++c) {
-      const size_t idx = vm_index<NCB>(e, 2 * c + hp, x);
-      acc[c] += BF16 ? bf_bits_to_f(reinterpret_cast<const unsigned short*>(X)[idx]) : reinterpret_cast<const float*>(X)[idx];
+    for (int c = 0; c < S::NPASS; ++c) {
+      S::fetch(X, ea, c, hp, x, &va[c * S::PER]);
+      S::fetch(X, eb, c, hp, x, &vb[c * S::PER]);
     }
+#pragma unroll
+    for (int c = 0; c < NV; ++c) { acc[c] += va[c]; acc[c] += vb[c]; }
+  }
+  if (t < t1) {
+    const size_t ea = perm ? (size_t)perm[t] : (size_t)t;
+    float va[NV];
+#pragma unroll
+    for (int c = 0; c < S::NPASS; ++c) S::fetch(X, ea, c, hp, x, &va[c * S::PER]);
+#pragma unroll
+    for (int c = 0; c < NV; ++c) acc[c] += va[c];
   }
 #pragma unroll
-  for (int c = 0; c < NC; ++c) out[(size_t)i * ldo + (2 * c + hp) * 32 + x] = acc[c];
+  for (int c = 0; c < S::NPASS; ++c)
+#pragma unroll
+    for (int k = 0; k < S::PER; ++k) out[(size_t)i * ldo + S::column(c, hp, x, k)] = acc[c * S::PER + k];
 }
 
 int32_t launch_segsum_vm(hipStream_t st, int H, bool bf16, int N, const int32_t* ptr, const int32_t* perm,
@@ -602,7 +649,11 @@ __global__ void __launch_bounds__(256) k_edge_bwd(EdgeBwdArgs p, int ntiles) {
           for (int ii = 0; ii < 4; ++ii) ok |= (e4 + ii < E ? 1u : 0u) << (4 * jj + ii);
         }
         float gm[C::CB][8];
+        unsigned zw[8];   // PAIRS: z2 of both column blocks, one word per edge
         if constexpr (PAIRS) {
+          const unsigned* zp = reinterpret_cast<const unsigned*>(p.z2_vm) + (((size_t)eb * (C::NCB / 2) + wc) * 16 + 8 * vh) * 64 + lane;
+#pragma unroll
+          for (int u = 0; u < 8; ++u) zw[u] = __builtin_nontemporal_load(zp + u * 64);
           const unsigned* __restrict__ U = reinterpret_cast<const unsigned*>(p.gM);
 #pragma unroll
           for (int u = 0; u < 8; ++u) {
@@ -623,10 +674,15 @@ __global__ void __launch_bounds__(256) k_edge_bwd(EdgeBwdArgs p, int ntiles) {
           const int n = cblk * 32 + x;
           const size_t zbase = (((size_t)eb * C::NCB + cblk) * 16 + 8 * vh) * 64 + lane;
           float zz[8], vals[8];
+          if constexpr (PAIRS) {
 #pragma unroll
-          for (int u = 0; u < 8; ++u)
-            zz[u] = BF16 ? bf_bits_to_f(__builtin_nontemporal_load(reinterpret_cast<const unsigned short*>(p.z2_vm) + zbase + u * 64))
-                         : __builtin_nontemporal_load(reinterpret_cast<const float*>(p.z2_vm) + zbase + u * 64);
+            for (int u = 0; u < 8; ++u) zz[u] = j == 0 ? __uint_as_float(zw[u] << 16) : __uint_as_float(zw[u] & 0xffff0000u);
+          } else {
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+              zz[u] = BF16 ? bf_bits_to_f(__builtin_nontemporal_load(reinterpret_cast<const unsigned short*>(p.z2_vm) + zbase + u * 64))
+                           : __builtin_nontemporal_load(reinterpret_cast<const float*>(p.z2_vm) + zbase + u * 64);
+          }
 #pragma unroll
           for (int u = 0; u < 8; ++u) {
             float m, dm;
@@ -669,28 +725,35 @@ __global__ void __launch_bounds__(256) k_edge_bwd(EdgeBwdArgs p, int ntiles) {
         }
         float z[C::CB][8];
         gather_z1<H, C::CB, PAIRS>(p.PQ, di, ci, dd, w1d, wc, x, z);
+        float gv[C::CB][8];
 #pragma unroll
-        for (int j = 0; j < C::CB; ++j) {
-          const size_t base = (((size_t)eb * C::NCB + (wc * C::CB + j)) * 16 + 8 * vh) * 64 + lane;
-          float gv[8];
+        for (int j = 0; j < C::CB; ++j)
 #pragma unroll
           for (int u = 0; u < 8; ++u) {
-            const float gz1 = acc[i][j][8 * vh + u] * dsilu_f(z[j][u]);   // rows beyond E have acc == 0
-            gv[u] = gz1;
-            sw1[j] += dd[u] * gz1;
+            gv[j][u] = acc[i][j][8 * vh + u] * dsilu_f(z[j][u]);   // rows beyond E have acc == 0
+            sw1[j] += dd[u] * gv[j][u];
           }
-          if constexpr (BF16) {
-            unsigned short* o = reinterpret_cast<unsigned short*>(p.gz1_vm) + base;
+        if constexpr (PAIRS) {
+          unsigned* o = reinterpret_cast<unsigned*>(p.gz1_vm) + (((size_t)eb * (C::NCB / 2) + wc) * 16 + 8 * vh) * 64 + lane;
 #pragma unroll
-            for (int t = 0; t < 4; ++t) {
-              const unsigned pk = pack_bf16x2(gv[2 * t], gv[2 * t + 1]);
-              __builtin_nontemporal_store((unsigned short)(pk & 0xffffu), o + (2 * t) * 64);
-              __builtin_nontemporal_store((unsigned short)(pk >> 16), o + (2 * t + 1) * 64);
+          for (int u = 0; u < 8; ++u) __builtin_nontemporal_store(pack_bf16x2(gv[0][u], gv[1][u]), o + u * 64);
+        } else {
+#pragma unroll
+          for (int j = 0; j < C::CB; ++j) {
+            const size_t base = (((size_t)eb * C::NCB + (wc * C::CB + j)) * 16 + 8 * vh) * 64 + lane;
+            if constexpr (BF16) {
+              unsigned short* o = reinterpret_cast<unsigned short*>(p.gz1_vm) + base;
+#pragma unroll
+              for (int t = 0; t < 4; ++t) {
+                const unsigned pk = pack_bf16x2(gv[j][2 * t], gv[j][2 * t + 1]);
+                __builtin_nontemporal_store((unsigned short)(pk & 0xffffu), o + (2 * t) * 64);
+                __builtin_nontemporal_store((unsigned short)(pk >> 16), o + (2 * t + 1) * 64);
+              }
+            } else {
+              float* o = reinterpret_cast<float*>(p.gz1_vm) + base;
+#pragma unroll
+              for (int u = 0; u < 8; ++u) __builtin_nontemporal_store(gv[j][u], o + u * 64);
             }
-          } else {
-            float* o = reinterpret_cast<float*>(p.gz1_vm) + base;
-#pragma unroll
-            for (int u = 0; u < 8; ++u) __builtin_nontemporal_store(gv[u], o + u * 64);
           }
         }
       }
