@@ -23,30 +23,72 @@ PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
 
 
 def kernel_work(tag, N, E, H, dtype):
-    """Algorithmic work of ONE launch of a kernel class: ('mfma', flops) or ('hbm', bytes)."""
-    f = 4
-    if tag in ("gemm_edge", "wgrad_edge"):
-        return "mfma", 2.0 * E * H * H
-    if tag == "edge_fused_fwd":
-        return "mfma", 2.0 * E * H * H
-    if tag == "edge_fused_bwd":
-        return "mfma", 4.0 * E * H * H
-    if tag == "seg_fwd":
-        return "hbm", E * (H + 3) * f + (N + 1) * 4 + N * (H + 3) * f
+    """Algorithmic work of ONE launch of a kernel class: (flops on the matrix cores, HBM bytes).
+
+    Bytes are what the method has to move for that kernel: every edge tensor it streams once (b bytes
+    per element, b = 2 for bf16 operands, 4 for fp32), the per-edge index/scalar arrays, and the node
+    tensors it gathers counted once (compulsory traffic; re-reads are cache traffic)."""
+    b = 2 if dtype == "bf16" else 4
+    EH, NH = float(E) * H, float(N) * H
+    if tag == "edge_fused_fwd":      # out: a1, z2; in: dst, col, d2; gathers P|Q
+        return 2.0 * EH * H, 2 * EH * b + 12.0 * E + 2 * NH * b
+    if tag == "edge_fused_bwd":      # in: z2, dst, col, d2, c; out: g_z2, g_z1; gathers P|Q, g_M
+        return 4.0 * EH * H, 3 * EH * b + 16.0 * E + 3 * NH * b
+    if tag == "wgrad_edge":          # in: a1, g_z2; out: H x H
+        return 2.0 * EH * H, 2 * EH * b + 4.0 * H * H
+    if tag == "seg_fwd":             # in: z2, rvec, row_ptr; out: M, v
+        return 0.0, EH * b + 12.0 * E + 4.0 * (N + 1) + (NH + 6.0 * N) * 4
     if tag in ("segsum_dst", "segsum_src"):
-        return "hbm", E * H * f + N * H * f + (N + 1) * 4 + (4 * E if tag == "segsum_src" else 0)
-    if tag == "edge_pre":
-        return "hbm", E * H * f + 12 * E + N * 2 * H * f
-    if tag == "edge_gz2":
-        return "hbm", 2 * E * H * f + 16 * E + N * H * f
+        return 0.0, EH * b + 4.0 * (N + 1) + NH * 4 + (4.0 * E if tag == "segsum_src" else 0.0)
+    if tag == "gemm_node":           # one H x H block product per atom row, fp32 in / out
+        return 2.0 * NH * H, 2 * NH * 4
+    if tag == "wgrad_node":
+        return 2.0 * NH * H, 2 * NH * 4
     if tag == "colsum":
-        return "hbm", E * H * f
-    if tag in ("neigh_count", "neigh_fill", "neigh_emit", "neigh_transpose", "neigh_setup"):
-        return "hbm", 12 * N + 27 * E + 8 * N
-    return "hbm", 0.0
+        return 0.0, NH * 4
+    if tag.startswith("neigh"):      # whole graph build: in pos; out col, shift, d2, rvec, dst, permT, offsets
+        return 0.0, 12.0 * N + 31.0 * E + 12.0 * N
+    return 0.0, 0.0
 
 
-def cpu_baseline(P, target_edges=30000):
+def roofline_of(tag, avg_s, N, E, H, dtype, traffic=None):
+    flops, nbytes = kernel_work(tag, N, E, H, dtype)
+    t_mfma = flops / (PEAK_TFLOPS[dtype] * 1e12)
+    t_hbm = nbytes / (PEAK_HBM_GBS * 1e9)
+    if t_mfma > t_hbm:
+        ach, peak, unit, bound, work = flops / avg_s / 1e12, PEAK_TFLOPS[dtype], "TFLOP/s", "mfma", flops
+    else:
+        ach, peak, unit, bound, work = nbytes / avg_s / 1e9, PEAK_HBM_GBS, "GB/s", "hbm", nbytes
+    return {"kernel": tag, "bound": bound, "achieved": ach, "peak": peak, "unit": unit, "frac": ach / peak,
+            "traffic": traffic, "avg_launch_ms": avg_s * 1e3, "work_per_launch": work,
+            "flops_per_launch": flops, "algorithmic_bytes_per_launch": nbytes}
+
+
+def read_traffic(config, tag):
+    """HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/)."""
+    path = os.path.join(ROOT, "profiles", f"traffic_{config}.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        f = line.split()
+        if len(f) >= 2 and f[0] == tag:
+            return float(f[1])
+    return None
+
+
+def calib_copy():
+    """A plain device-to-device copy of known size, for calibrating the FETCH_SIZE / WRITE_SIZE counters."""
+    import torch
+    n = 1 << 28   # 1 GiB of float32 read + 1 GiB written per copy
+    a = torch.ones(n, dtype=torch.float32, device="cuda")
+    b = torch.empty_like(a)
+    for _ in range(5):
+        b.copy_(a)
+    torch.cuda.synchronize()
+    print(json.dumps({"calib_copy_bytes_read": n * 4, "calib_copy_bytes_written": n * 4, "copies": 5}))
+
+
+def cpu_baseline(P, target_edges=150000):
     """The oracle, as it stands, on a bounded sample (the first graphs of the same batch)."""
     import numpy as np
     import oracle
@@ -83,12 +125,16 @@ def main():
     ap.add_argument("--config", default="cfg4")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--breakdown", action="store_true", help="print the per-kernel-class split to stderr")
+    ap.add_argument("--calib-copy", action="store_true", help="only run a 1 GiB copy kernel (counter calibration)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; no figure at several GPUs exists (--gpus 1 only)",
               file=sys.stderr)
         sys.exit(2)
 
+    if args.calib_copy:
+        calib_copy()
+        return
     import torch
     from parity_util import gpu_hotpath, problem_from_config
     from paper_2506_21788_amd import binding as B
@@ -138,15 +184,9 @@ def main():
     torch.cuda.synchronize()
     t_mp = (time.perf_counter() - t0) / args.steps
 
-    bound, work = kernel_work(dom, N, E, H, hp["dtype"])
     avg_s = dom_ms / max(dom_n, 1) * 1e-3
-    if bound == "mfma":
-        peak, unit, ach = PEAK_TFLOPS[hp["dtype"]], "TFLOP/s", work / avg_s / 1e12
-    else:
-        peak, unit, ach = PEAK_HBM_GBS, "GB/s", work / avg_s / 1e9
-    roofline = {"kernel": dom, "bound": bound, "achieved": ach, "peak": peak, "unit": unit, "frac": ach / peak,
-                "traffic": None, "avg_launch_ms": avg_s * 1e3, "launches_per_step": dom_n / args.steps,
-                "work_per_launch": work}
+    roofline = roofline_of(dom, avg_s, N, E, H, hp["dtype"], read_traffic(args.config, dom))
+    roofline["launches_per_step"] = dom_n / args.steps
 
     out = {
         "metric": "message-passing edges/s (fwd+bwd), whole step incl. neighbour search, 1 MI355X",
@@ -165,11 +205,10 @@ def main():
         out["cpu_baseline"] = cpu_baseline(P)
     if args.breakdown:
         for k, v in sorted(split.items(), key=lambda kv: -kv[1]["ms_per_step"]):
-            bd, w = kernel_work(k, N, E, H, hp["dtype"])
             per = v["ms_per_step"] / v["launches_per_step"] * 1e-3
-            rate = (w / per / 1e12, "TFLOP/s") if bd == "mfma" else (w / per / 1e9, "GB/s")
+            r = roofline_of(k, per, N, E, H, hp["dtype"])
             print(f"{k:18s} {v['launches_per_step']:6.1f} launches  {v['ms_per_step']:9.3f} ms/step  "
-                  f"{rate[0]:10.1f} {rate[1]}", file=sys.stderr)
+                  f"{r['achieved']:10.1f} {r['unit']:8s} {100 * r['frac']:5.1f} % of {r['bound']} peak", file=sys.stderr)
     print(json.dumps(out))
 
 

@@ -9,6 +9,9 @@
 //                    fp32: (((eb*(H/32) + cb)*4 + v/4)*64 + l)*4 + v%4
 // The operand-packed form is, unchanged, the A/B operand of the matrix-core instruction that
 // contracts over edges (the weight-gradient product), so that product needs no transpose and no LDS.
+// With bf16 operands and H = 256 (two column blocks per lane, see edge_pairs()) the v-major tensors hold
+// one 32-bit word per lane and register instead: ((eb*(H/64) + wc)*16 + v)*64 + l, the bf16 pair of columns
+// wc*64 + (l&31) and wc*64 + 32 + (l&31).
 // E is padded to a multiple of 32 in these buffers; padded edges hold zeros where they are summed.
 #pragma once
 

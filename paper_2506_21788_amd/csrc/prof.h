@@ -17,13 +17,10 @@ enum ProfTag : int {
   PT_NEIGH_TRANSPOSE,   // source-sorted plan
   PT_PACK,              // weight packing
   PT_GEMM_NODE,         // row-tile GEMM over atoms / graphs
-  PT_GEMM_EDGE,         // row-tile GEMM over edges
   PT_WGRAD_NODE,        // transposed GEMM over atoms / graphs (+ its partial reduction)
   PT_WGRAD_EDGE,        // transposed GEMM over edges (+ its partial reduction)
   PT_COLSUM,            // column sums (bias and vector gradients)
-  PT_EDGE_PRE,          // per-edge gather + SiLU
   PT_SEG_FWD,           // destination-sorted segmented reduction of messages
-  PT_EDGE_GZ2,          // per-edge backward elementwise
   PT_SEGSUM_DST,        // destination-sorted segmented sum (backward)
   PT_SEGSUM_SRC,        // source-sorted (transpose) segmented sum (backward)
   PT_HEAD_OUT,          // head output layers

@@ -32,8 +32,8 @@ hipEvent_t get_event() {
 
 const char* const kNames[PT_COUNT] = {
     "neigh_setup", "neigh_count", "neigh_fill", "neigh_emit", "neigh_transpose", "pack", "gemm_node",
-    "gemm_edge", "wgrad_node", "wgrad_edge", "colsum", "edge_pre", "seg_fwd", "edge_gz2", "segsum_dst",
-    "segsum_src", "head_out", "pool", "embed", "misc", "edge_fused_fwd", "edge_fused_bwd"};
+    "wgrad_node", "wgrad_edge", "colsum", "seg_fwd", "segsum_dst", "segsum_src", "head_out", "pool", "embed",
+    "misc", "edge_fused_fwd", "edge_fused_bwd"};
 }  // namespace
 
 void prof_record(int tag, hipStream_t st, bool start) {
