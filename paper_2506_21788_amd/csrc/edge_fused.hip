@@ -788,7 +788,7 @@ static int32_t launch_edge_bwd_t(hipStream_t st, const EdgeBwdArgs& a) {
                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES));
     attr_set = true;
   }
-  int64_t grid = (int64_t)num_cus() * 4;
+  int64_t grid = (int64_t)num_cus() * 2;   // two workgroups are resident per CU
   if (grid > EDGE_BWD_MAX_GRID) grid = EDGE_BWD_MAX_GRID;
   if (grid > ntiles) grid = ntiles;
   if (grid < 1) grid = 1;  // E == 0: one block writes zero partials

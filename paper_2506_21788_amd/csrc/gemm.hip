@@ -61,6 +61,18 @@ int32_t launch_pack(hipStream_t st, int H, bool bf16, const PackArgs& a, int gro
 // ---------------------------------------------------------------------------------------------
 // row-tile GEMM
 // ---------------------------------------------------------------------------------------------
+// 32-bit byte offsets from a uniform base (row * pitch fits 24 x 24 -> 32 bits for every node tensor here):
+// one full-rate multiply per row instead of 64-bit index arithmetic per element
+__device__ __forceinline__ float ld_f32(const float* base, unsigned byte_off) {
+  return *reinterpret_cast<const float*>(reinterpret_cast<const char*>(base) + byte_off);
+}
+__device__ __forceinline__ float4 ld_f32x4(const float* base, unsigned byte_off) {
+  return *reinterpret_cast<const float4*>(reinterpret_cast<const char*>(base) + byte_off);
+}
+__device__ __forceinline__ void st_f32(float* base, unsigned byte_off, float v) {
+  *reinterpret_cast<float*>(reinterpret_cast<char*>(base) + byte_off) = v;
+}
+
 template <int H, bool BF16>
 struct GemmCfg {
   static constexpr int TM = 64;
@@ -305,7 +317,7 @@ struct ReduceArgs {
   long grp_dest_stride;
 };
 
-__global__ void k_reduce_partials(ReduceArgs a) {
+__global__ void __launch_bounds__(256) k_reduce_partials(ReduceArgs a) {
   const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
   const int blk = blockIdx.y, grp = blockIdx.z;
   if (i >= a.blk_elems) return;
@@ -325,6 +337,35 @@ __global__ void k_reduce_partials(ReduceArgs a) {
   a.dest[blk][grp * a.grp_dest_stride + i] = s;
 }
 
+// Few elements, many partials (bias-type sums): 4 threads per element take a contiguous quarter of the
+// partials each (in order), then the quarters are added in order.
+__global__ void __launch_bounds__(256) k_reduce_partials_tall(ReduceArgs a) {
+  __shared__ float sh[256];
+  const int blk = blockIdx.y, grp = blockIdx.z;
+  const int e = threadIdx.x & 63, ph = threadIdx.x >> 6;
+  const long i = (long)blockIdx.x * 64 + e;
+  const int per = (a.nsplit + 3) / 4;
+  const int k0 = ph * per;
+  const int k1 = k0 + per < a.nsplit ? k0 + per : a.nsplit;
+  float s = 0.f;
+  if (i < a.blk_elems) {
+    const float* p = a.partial + ((long)grp * a.nsplit * a.nblk + blk) * a.blk_elems + i;
+    const long step = (long)a.nblk * a.blk_elems;
+    int k = k0;
+    for (; k + 16 <= k1; k += 16) {
+      float v[16];
+#pragma unroll
+      for (int u = 0; u < 16; ++u) v[u] = p[(long)(k + u) * step];
+#pragma unroll
+      for (int u = 0; u < 16; ++u) s += v[u];
+    }
+    for (; k < k1; ++k) s += p[(long)k * step];
+  }
+  sh[threadIdx.x] = s;
+  __syncthreads();
+  if (ph == 0 && i < a.blk_elems) a.dest[blk][grp * a.grp_dest_stride + i] = ((sh[e] + sh[64 + e]) + sh[128 + e]) + sh[192 + e];
+}
+
 int32_t launch_reduce_partials(hipStream_t st, const float* partial, int nsplit, int nblk, long blk_elems,
                                float* const dest[4], int groups, long grp_dest_stride) {
   ReduceArgs r;
@@ -334,7 +375,10 @@ int32_t launch_reduce_partials(hipStream_t st, const float* partial, int nsplit,
   r.blk_elems = blk_elems;
   for (int i = 0; i < 4; ++i) r.dest[i] = dest[i];
   r.grp_dest_stride = grp_dest_stride;
-  k_reduce_partials<<<dim3((unsigned)((blk_elems + 255) / 256), nblk, groups), 256, 0, st>>>(r);
+  if (blk_elems <= 1024 && nsplit >= 64)
+    k_reduce_partials_tall<<<dim3((unsigned)((blk_elems + 63) / 64), nblk, groups), 256, 0, st>>>(r);
+  else
+    k_reduce_partials<<<dim3((unsigned)((blk_elems + 255) / 256), nblk, groups), 256, 0, st>>>(r);
   HGNN_LAUNCH_CHECK("k_reduce_partials");
   return HGNN_OK;
 }
@@ -491,16 +535,7 @@ static int32_t launch_wgrad_t(hipStream_t st, const WgradArgs& a) {
   ProfScope ps(a.tag, st);
   k_wgrad<H, BF16><<<dim3(nsplit, nblk * C::TILES * C::TILES, groups), 256, 0, st>>>(a, nsplit, (int)rps);
   HGNN_LAUNCH_CHECK("k_wgrad");
-  ReduceArgs r;
-  r.partial = a.partial;
-  r.nsplit = nsplit;
-  r.nblk = nblk;
-  r.blk_elems = (long)H * H;
-  for (int i = 0; i < 4; ++i) r.dest[i] = a.dest[i];
-  r.grp_dest_stride = a.grp_dest_stride;
-  k_reduce_partials<<<dim3((H * H + 255) / 256, nblk, groups), 256, 0, st>>>(r);
-  HGNN_LAUNCH_CHECK("k_reduce_partials");
-  return HGNN_OK;
+  return launch_reduce_partials(st, a.partial, nsplit, nblk, (long)H * H, a.dest, groups, a.grp_dest_stride);
 }
 
 int32_t launch_wgrad(hipStream_t st, int H, bool bf16, const WgradArgs& a) {
@@ -561,7 +596,7 @@ __global__ void __launch_bounds__(256) k_colsum(ColsumArgs p, int H, int nsplit,
 }
 
 static int colsum_splits(int64_t M) {
-  int64_t s = (M + 63) / 64;
+  int64_t s = (M + 255) / 256;
   if (s < 1) s = 1;
   if (s > 1024) s = 1024;
   return (int)s;
@@ -579,17 +614,8 @@ int32_t launch_colsum(hipStream_t st, int H, const ColsumArgs& a) {
   ProfScope ps(PT_COLSUM, st);
   k_colsum<<<dim3(nsplit, groups), 256, 0, st>>>(a, H, nsplit, (int)rps);
   HGNN_LAUNCH_CHECK("k_colsum");
-  ReduceArgs r;
-  r.partial = a.partial;
-  r.nsplit = nsplit;
-  r.nblk = 1;
-  r.blk_elems = H;
-  r.dest[0] = a.dest;
-  r.dest[1] = r.dest[2] = r.dest[3] = nullptr;
-  r.grp_dest_stride = a.grp_dest_stride;
-  k_reduce_partials<<<dim3((H + 255) / 256, 1, groups), 256, 0, st>>>(r);
-  HGNN_LAUNCH_CHECK("k_reduce_partials");
-  return HGNN_OK;
+  float* dest[4] = {a.dest, nullptr, nullptr, nullptr};
+  return launch_reduce_partials(st, a.partial, nsplit, 1, H, dest, groups, a.grp_dest_stride);
 }
 
 }  // namespace hgnn

@@ -301,15 +301,22 @@ k_head_out_bwd(int N, int G, int Hh, const float* __restrict__ ze, const float* 
   for (int c = lane; c < Hh; c += 64) gz_[c] = go * w2[c] * dsilu_f(z[c]);
 }
 
-// dest[s*stride] = sum over positions of group s of w[row_idx[pos]]   (one wavefront per group)
-__global__ void k_group_scalar_sum(const float* __restrict__ w, const int32_t* __restrict__ row_idx,
-                                   const int32_t* __restrict__ grp_ptr, float* __restrict__ dest, long stride) {
+// dest[s*stride] = sum over positions of group s of w[row_idx[pos]]   (one block per group, fixed order)
+__global__ void __launch_bounds__(1024)
+k_group_scalar_sum(const float* __restrict__ w, const int32_t* __restrict__ row_idx,
+                   const int32_t* __restrict__ grp_ptr, float* __restrict__ dest, long stride) {
+  __shared__ float sh[16];
   const int s = blockIdx.x;
-  const int lane = threadIdx.x;
   float acc = 0.f;
-  for (int t = grp_ptr[s] + lane; t < grp_ptr[s + 1]; t += 64) acc += w[row_idx[t]];
+  for (int t = grp_ptr[s] + threadIdx.x; t < grp_ptr[s + 1]; t += 1024) acc += w[row_idx[t]];
   acc = wsum(acc);
-  if (lane == 0) dest[s * stride] = acc;
+  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = acc;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float tot = 0.f;
+    for (int k = 0; k < 16; ++k) tot += sh[k];
+    dest[s * stride] = tot;
+  }
 }
 
 struct HeadSaved {
@@ -568,7 +575,7 @@ extern "C" int32_t hgnn_multihead_decode_bwd(void* stream, int32_t N, int32_t G,
       c.X = z; c.ldx = Hh; c.f_silu = 1; c.w = gout; c.row_idx = ridx; c.grp_ptr = gptr; c.S = S; c.M = M;
       c.dest = gWhead + oW2; c.grp_dest_stride = o.per; c.partial = w.partial;
       HGNN_TRY(launch_colsum(st, Hh, c));
-      k_group_scalar_sum<<<S, 64, 0, st>>>(gout, ridx, gptr, gWhead + ob2, o.per);
+      k_group_scalar_sum<<<S, 1024, 0, st>>>(gout, ridx, gptr, gWhead + ob2, o.per);
       HGNN_LAUNCH_CHECK("k_group_scalar_sum");
     }
     {  // first layer bias and weight

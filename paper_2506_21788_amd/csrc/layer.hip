@@ -60,7 +60,8 @@ struct LayerWs {
   float* g_hM;     // [N,2H]
   unsigned* gM_pk; // [N,H/2] words: g_M as bf16 pairs (only when the fused kernels gather pairs)
   float* g_PQ;     // [N,2H]
-  float* partial;  // split-K / column-sum partials
+  float* partial;  // split-K / column-sum partials of the main stream
+  float* partial2; // the same for the work that runs on the side stream
   size_t bytes;
 };
 
@@ -79,8 +80,33 @@ static LayerWs carve_ws(void* p, int N, int64_t E, int H, bool bf16) {
   const size_t cands[3] = {colsum_partial_floats(H, N, 1), wgrad_frag_partial_floats(H), edge_bwd_colpart_floats(H)};
   for (size_t x : cands) pf = x > pf ? x : pf;
   w.partial = c.take<float>(pf);
+  w.partial2 = c.take<float>(pf);
   w.bytes = c.used();
   return w;
+}
+
+// Weight gradients are off the critical path of the reverse pass (nothing downstream reads them), so they run
+// on a library-owned side stream (default priority) that forks from and joins the caller's stream through
+// events: they overlap the latency-bound kernels of the main chain. Everything stays asynchronous to the host.
+struct SideStream {
+  hipStream_t s = nullptr;
+  hipEvent_t ev[8] = {};
+  bool ok = false;
+};
+static SideStream& side_stream() {
+  static SideStream ss;
+  if (!ss.ok) {
+    bool good = hipStreamCreateWithFlags(&ss.s, hipStreamNonBlocking) == hipSuccess;
+    for (auto& e : ss.ev) good = good && hipEventCreateWithFlags(&e, hipEventDisableTiming) == hipSuccess;
+    ss.ok = good;
+  }
+  return ss;
+}
+// `to` waits for everything enqueued on `from` so far
+static int32_t stream_after(hipStream_t to, hipStream_t from, hipEvent_t ev) {
+  HGNN_HIP(hipEventRecord(ev, from));
+  HGNN_HIP(hipStreamWaitEvent(to, ev, 0));
+  return HGNN_OK;
 }
 
 static int32_t check_layer_args(int N, int64_t E, int H, int dtype) {
@@ -218,7 +244,24 @@ extern "C" int32_t hgnn_mp_layer_bwd(void* stream, int32_t N, int64_t E, int32_t
   pk.d[5] = {o.W1 + HH, 1, H};
   HGNN_TRY(launch_pack(st, H, bf16, pk));
 
+  SideStream& ss = side_stream();
+  HGNN_REQUIRE(ss.ok, HGNN_ERR_HIP, "could not create the side stream");
+  hipStream_t sx = ss.s;
+  HGNN_TRY(stream_after(sx, st, ss.ev[0]));   // inputs of this call are ready on the side stream too
+
   // every gradient field is written below even when there is nothing to sum over
+  {  // side: gW4 = silu(z3)^T g_h' ; gb4   (inputs only)
+    WgradArgs a;
+    a.A[0] = s.z3; a.lda[0] = H; a.a_silu = 1;
+    a.B[0] = g_h_out; a.ldb[0] = H;
+    a.M = N;
+    a.dest[0] = gW + o.W4;
+    a.partial = w.partial2;
+    HGNN_TRY(launch_wgrad(sx, H, bf16, a));
+    ColsumArgs c;
+    c.X = g_h_out; c.ldx = H; c.M = N; c.dest = gW + o.b4; c.partial = w.partial2;
+    HGNN_TRY(launch_colsum(sx, H, c));
+  }
   {  // g_z3 = (g_h' W4^T) * silu'(z3)
     GemmArgs g;
     g.A[0] = g_h_out; g.lda[0] = H;
@@ -228,17 +271,18 @@ extern "C" int32_t hgnn_mp_layer_bwd(void* stream, int32_t N, int64_t E, int32_t
     g.C = w.g_z3; g.ldc = H;
     HGNN_TRY(launch_gemm(st, H, bf16, g));
   }
-  {  // gW4 = silu(z3)^T g_h' ; gb4
+  HGNN_TRY(stream_after(sx, st, ss.ev[1]));
+  {  // side: gW3 = [h ; M]^T g_z3 ; gb3
     WgradArgs a;
-    a.A[0] = s.z3; a.lda[0] = H; a.a_silu = 1;
-    a.B[0] = g_h_out; a.ldb[0] = H;
+    a.A[0] = h_in; a.lda[0] = H; a.A[1] = s.M; a.lda[1] = H; a.nA = 2;
+    a.B[0] = w.g_z3; a.ldb[0] = H;
     a.M = N;
-    a.dest[0] = gW + o.W4;
-    a.partial = w.partial;
-    HGNN_TRY(launch_wgrad(st, H, bf16, a));
+    a.dest[0] = gW + o.W3; a.dest[1] = gW + o.W3 + HH;
+    a.partial = w.partial2;
+    HGNN_TRY(launch_wgrad(sx, H, bf16, a));
     ColsumArgs c;
-    c.X = g_h_out; c.ldx = H; c.M = N; c.dest = gW + o.b4; c.partial = w.partial;
-    HGNN_TRY(launch_colsum(st, H, c));
+    c.X = w.g_z3; c.ldx = H; c.M = N; c.dest = gW + o.b3; c.partial = w.partial2;
+    HGNN_TRY(launch_colsum(sx, H, c));
   }
   {  // [g_h(a) | g_M] = g_z3 W3^T
     GemmArgs g;
@@ -251,19 +295,7 @@ extern "C" int32_t hgnn_mp_layer_bwd(void* stream, int32_t N, int64_t E, int32_t
     }
     HGNN_TRY(launch_gemm(st, H, bf16, g));
   }
-  {  // gW3 = [h ; M]^T g_z3 ; gb3
-    WgradArgs a;
-    a.A[0] = h_in; a.lda[0] = H; a.A[1] = s.M; a.lda[1] = H; a.nA = 2;
-    a.B[0] = w.g_z3; a.ldb[0] = H;
-    a.M = N;
-    a.dest[0] = gW + o.W3; a.dest[1] = gW + o.W3 + HH;
-    a.partial = w.partial;
-    HGNN_TRY(launch_wgrad(st, H, bf16, a));
-    ColsumArgs c;
-    c.X = w.g_z3; c.ldx = H; c.M = N; c.dest = gW + o.b3; c.partial = w.partial;
-    HGNN_TRY(launch_colsum(st, H, c));
-  }
-  // edge part: c_e, then g_z2 -> (x W2^T) -> g_z1 with the per-column sums, then g_W2, then the two segment sums
+  // edge part: c_e, then g_z2 -> (x W2^T) -> g_z1 with the per-column sums
   HGNN_TRY(launch_edge_cvec(st, E, dst, rvec, g_v_out, alpha, w.cvec));
   {
     EdgeBwdArgs e;
@@ -279,24 +311,25 @@ extern "C" int32_t hgnn_mp_layer_bwd(void* stream, int32_t N, int64_t E, int32_t
     e.g_b2 = gW + o.b2; e.g_wx = gW + o.wx; e.g_w1d = gW + o.W1 + 2 * HH;
     HGNN_TRY(launch_edge_bwd(st, H, bf16, e));
   }
-  HGNN_TRY(launch_wgrad_frag(st, H, bf16, E, s.a1_pk, w.gz2_pk, w.partial, gW + o.W2));
+  HGNN_TRY(stream_after(sx, st, ss.ev[2]));
+  // side: g_W2 = a1^T g_z2 streams while the main stream runs the two segment sums
+  HGNN_TRY(launch_wgrad_frag(sx, H, bf16, E, s.a1_pk, w.gz2_pk, w.partial2, gW + o.W2));
   HGNN_TRY(launch_segsum_vm(st, H, bf16, N, row_ptr, nullptr, w.gz1_vm, w.g_PQ, 2 * H, PT_SEGSUM_DST));     // g_P
   HGNN_TRY(launch_segsum_vm(st, H, bf16, N, colT_ptr, permT, w.gz1_vm, w.g_PQ + H, 2 * H, PT_SEGSUM_SRC));  // g_Q
-  {
-    ColsumArgs c2;  // gb1 = sum_i g_P_i
-    c2.X = w.g_PQ; c2.ldx = 2 * H; c2.M = N; c2.dest = gW + o.b1; c2.partial = w.partial;
-    HGNN_TRY(launch_colsum(st, H, c2));
-  }
-  {  // gW1a = h^T g_P ; gW1b = h^T g_Q
+  HGNN_TRY(stream_after(sx, st, ss.ev[3]));
+  {  // side: gb1 = sum_i g_P_i ; gW1a = h^T g_P ; gW1b = h^T g_Q
+    ColsumArgs c2;
+    c2.X = w.g_PQ; c2.ldx = 2 * H; c2.M = N; c2.dest = gW + o.b1; c2.partial = w.partial2;
+    HGNN_TRY(launch_colsum(sx, H, c2));
     WgradArgs a;
     a.A[0] = h_in; a.lda[0] = H;
     a.B[0] = w.g_PQ; a.ldb[0] = 2 * H; a.B[1] = w.g_PQ + H; a.ldb[1] = 2 * H; a.nB = 2;
     a.M = N;
     a.dest[0] = gW + o.W1; a.dest[1] = gW + o.W1 + HH;
-    a.partial = w.partial;
-    HGNN_TRY(launch_wgrad(st, H, bf16, a));
+    a.partial = w.partial2;
+    HGNN_TRY(launch_wgrad(sx, H, bf16, a));
   }
-  if (N > 0) {  // g_h = g_h' + g_h(a) + g_P W1a^T + g_Q W1b^T
+  {  // g_h = g_h' + g_h(a) + g_P W1a^T + g_Q W1b^T
     GemmArgs g;
     g.A[0] = w.g_PQ; g.lda[0] = 2 * H; g.A[1] = w.g_PQ + H; g.lda[1] = 2 * H; g.nkc = 2;
     g.B = w.packed; g.blk[0][0] = 4; g.blk[1][0] = 5;
@@ -306,6 +339,7 @@ extern "C" int32_t hgnn_mp_layer_bwd(void* stream, int32_t N, int64_t E, int32_t
     g.C = g_h_in; g.ldc = H;
     HGNN_TRY(launch_gemm(st, H, bf16, g));
   }
+  HGNN_TRY(stream_after(st, sx, ss.ev[4]));   // join: the caller's stream now also orders after every gradient
   if (g_v_in != g_v_out) HGNN_TRY(launch_copy_f32(st, g_v_out, g_v_in, (int64_t)N * 3));
   return HGNN_OK;
 }
