@@ -58,6 +58,19 @@ struct Carver {
 
 inline bool valid_H(int H) { return H == 64 || H == 128 || H == 256; }
 
+// compute units of the current device (asked once)
+inline int num_cus() {
+  static int n = 0;
+  if (n == 0) {
+    hipDeviceProp_t prop;
+    int dev = 0;
+    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
+      n = prop.multiProcessorCount;
+    if (n <= 0) n = 256;
+  }
+  return n;
+}
+
 // device-wide exclusive prefix sum of n int32 values; out has n+1 entries (out[n] = total).
 // scratch must hold scan_scratch_ints(n) ints.
 size_t scan_scratch_ints(int64_t n);

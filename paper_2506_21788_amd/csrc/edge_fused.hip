@@ -28,18 +28,6 @@ struct ECfg {
   static constexpr size_t LDS_BYTES = (size_t)TM * STRIDE * (BF16 ? 2 : 4);
 };
 
-static int num_cus() {
-  static int n = 0;
-  if (n == 0) {
-    hipDeviceProp_t prop;
-    int dev = 0;
-    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
-      n = prop.multiProcessorCount;
-    if (n <= 0) n = 256;
-  }
-  return n;
-}
-
 __device__ __forceinline__ float bf_bits_to_f(unsigned short b) { return __uint_as_float(((unsigned)b) << 16); }
 
 // the 4 consecutive per-edge scalars e4..e4+3 (e4 is a multiple of 4); zeros beyond E
@@ -286,7 +274,7 @@ __device__ __forceinline__ void lds_rows8(const int* s, int rblk, int vh, int g,
 // forward
 // ---------------------------------------------------------------------------------------------
 template <int H, bool BF16, bool BRES_REQ>
-__global__ void __launch_bounds__(256, 2) k_edge_fwd(EdgeFwdArgs p, int ntiles) {
+__global__ void __launch_bounds__(256, BRES_REQ ? 2 : 3) k_edge_fwd(EdgeFwdArgs p, int ntiles) {
   using C = ECfg<H, BF16>;
   constexpr bool BRES = BRES_REQ && (BF16 || H <= 128);   // keep this wavefront's slice of W2 in registers?
   constexpr bool PAIRS = BF16 && C::CB == 2;
@@ -403,12 +391,16 @@ static int32_t launch_edge_fwd_t(hipStream_t st, const EdgeFwdArgs& a) {
   if (!attr_set) {
     HGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_edge_fwd<H, BF16, true>),
                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)(C::LDS_BYTES + 6 * C::TM * 4)));
+    HGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_edge_fwd<H, BF16, false>),
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)(C::LDS_BYTES + 6 * C::TM * 4)));
     attr_set = true;
   }
-  int64_t grid = (int64_t)num_cus() * 4;
+  static const bool bres = [] { const char* e = getenv("HGNN_BRES"); return !(e && e[0] == '0'); }();
+  int64_t grid = (int64_t)num_cus() * (bres ? 4 : 3);
   if (grid > ntiles) grid = ntiles;
   ProfScope ps(PT_EDGE_FUSED_FWD, st);
-  k_edge_fwd<H, BF16, true><<<dim3((unsigned)grid), 256, C::LDS_BYTES + 6 * C::TM * 4, st>>>(a, (int)ntiles);
+  if (bres) k_edge_fwd<H, BF16, true><<<dim3((unsigned)grid), 256, C::LDS_BYTES + 6 * C::TM * 4, st>>>(a, (int)ntiles);
+  else k_edge_fwd<H, BF16, false><<<dim3((unsigned)grid), 256, C::LDS_BYTES + 6 * C::TM * 4, st>>>(a, (int)ntiles);
   HGNN_LAUNCH_CHECK("k_edge_fwd");
   return HGNN_OK;
 }
@@ -611,7 +603,7 @@ int32_t launch_edge_cvec(hipStream_t st, int64_t E, const int32_t* dst, const fl
 }
 
 template <int H, bool BF16>
-__global__ void __launch_bounds__(256) k_edge_bwd(EdgeBwdArgs p, int ntiles) {
+__global__ void __launch_bounds__(256, 3) k_edge_bwd(EdgeBwdArgs p, int ntiles) {
   using C = ECfg<H, BF16>;
   constexpr bool PAIRS = BF16 && C::CB == 2;
   extern __shared__ __align__(16) unsigned char smem[];
@@ -788,7 +780,7 @@ static int32_t launch_edge_bwd_t(hipStream_t st, const EdgeBwdArgs& a) {
                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES));
     attr_set = true;
   }
-  int64_t grid = (int64_t)num_cus() * 2;   // two workgroups are resident per CU
+  int64_t grid = (int64_t)num_cus() * 3;   // three workgroups are resident per CU
   if (grid > EDGE_BWD_MAX_GRID) grid = EDGE_BWD_MAX_GRID;
   if (grid > ntiles) grid = ntiles;
   if (grid < 1) grid = 1;  // E == 0: one block writes zero partials

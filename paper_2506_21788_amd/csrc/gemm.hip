@@ -73,9 +73,10 @@ __device__ __forceinline__ void st_f32(float* base, unsigned byte_off, float v) 
   *reinterpret_cast<float*>(reinterpret_cast<char*>(base) + byte_off) = v;
 }
 
-template <int H, bool BF16>
+// TM_ rows per workgroup tile: 64, or 96 where that makes the launch a whole number of resident rounds
+template <int H, bool BF16, int TM_ = 64>
 struct GemmCfg {
-  static constexpr int TM = 64;
+  static constexpr int TM = TM_;
   static constexpr int WC = (H / 32 < 4) ? H / 32 : 4;   // wavefronts side by side over columns
   static constexpr int WR = 4 / WC;                      // and over rows
   static constexpr int WROWS = TM / WR;
@@ -84,6 +85,7 @@ struct GemmCfg {
   static constexpr int CB = WCOLS / 32;
   static constexpr int STRIDE = BF16 ? H + 8 : H + 4;    // LDS row pitch in elements (bank spread)
   static constexpr size_t LDS_BYTES = (size_t)TM * STRIDE * (BF16 ? 2 : 4);
+  static_assert(WROWS % 32 == 0 && (TM * (H / 4)) % 256 == 0, "tile height does not fit the wavefront grid");
 };
 
 __device__ __forceinline__ bool tile_of_group(const int32_t* grp_ptr, int S, int TM, int tile, int& grp, int& rbeg,
@@ -102,9 +104,9 @@ __device__ __forceinline__ bool tile_of_group(const int32_t* grp_ptr, int S, int
   return false;
 }
 
-template <int H, bool BF16>
-__global__ void __launch_bounds__(256) k_gemm(GemmArgs p) {
-  using C = GemmCfg<H, BF16>;
+template <int H, bool BF16, int TM>
+__global__ void __launch_bounds__(256, 2) k_gemm(GemmArgs p) {
+  using C = GemmCfg<H, BF16, TM>;
   extern __shared__ __align__(16) unsigned char smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wr = wave / C::WC, wc = wave % C::WC;
@@ -133,7 +135,7 @@ __global__ void __launch_bounds__(256) k_gemm(GemmArgs p) {
     const int lda = p.lda[kc];
     constexpr int CH = H / 4;
     constexpr int ITER = C::TM * CH / 256;
-    constexpr int UN = ITER < 8 ? ITER : 8;
+    constexpr int UN = ITER % 8 == 0 ? 8 : (ITER % 6 == 0 ? 6 : (ITER % 4 == 0 ? 4 : (ITER % 2 == 0 ? 2 : 1)));
     static_assert(ITER % UN == 0, "staging loop must divide evenly");
     for (int it0 = 0; it0 < ITER; it0 += UN) {
       float4 v[UN];
@@ -172,7 +174,8 @@ __global__ void __launch_bounds__(256) k_gemm(GemmArgs p) {
     if (BF16) {
       const bf16x8_t* __restrict__ Bp = reinterpret_cast<const bf16x8_t*>(p.B) + bblk0 * (H * H / 8);
       constexpr int NKB = H / 16;
-#pragma unroll 8
+      constexpr int KUN = C::TM > 64 ? 4 : 8;   // operand loads in flight; fewer with the taller tile's accumulators
+#pragma unroll KUN
       for (int kb = 0; kb < NKB; ++kb) {
         bf16x8_t a[C::RB];
 #pragma unroll
@@ -243,7 +246,7 @@ __global__ void __launch_bounds__(256) k_gemm(GemmArgs p) {
   for (int i = 0; i < C::RB; ++i) {
     // the 16 rows of this lane in row block i (clamped to the last valid row so that every load below is
     // unconditional and all of them can be in flight together)
-    long grow[16];
+    int grow[16];
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
       const int r = wr * C::WROWS + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
@@ -259,9 +262,9 @@ __global__ void __launch_bounds__(256) k_gemm(GemmArgs p) {
       float mv[16], a1[16], a2[16];
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        mv[v] = p.mul ? p.mul[grow[v] * p.ldmul + gcol] : 1.f;
-        a1[v] = p.add1 ? p.add1[grow[v] * p.ldadd1 + gcol] : 0.f;
-        a2[v] = p.add2 ? p.add2[grow[v] * p.ldadd2 + gcol] : 0.f;
+        mv[v] = p.mul ? p.mul[(long)grow[v] * p.ldmul + gcol] : 1.f;
+        a1[v] = p.add1 ? p.add1[(long)grow[v] * p.ldadd1 + gcol] : 0.f;
+        a2[v] = p.add2 ? p.add2[(long)grow[v] * p.ldadd2 + gcol] : 0.f;
       }
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
@@ -269,28 +272,58 @@ __global__ void __launch_bounds__(256) k_gemm(GemmArgs p) {
         if (rbeg + r < rend) {
           float x = acc[i][j][v] + bv;
           if (p.mul) x *= p.mul_is_z ? dsilu_f(mv[v]) : mv[v];
-          p.C[grow[v] * p.ldc + gcol] = x + a1[v] + a2[v];
+          p.C[(long)grow[v] * p.ldc + gcol] = x + a1[v] + a2[v];
         }
       }
     }
   }
 }
 
-template <int H, bool BF16>
-static int32_t launch_gemm_t(hipStream_t st, const GemmArgs& a) {
-  using C = GemmCfg<H, BF16>;
-  if (a.M <= 0) return HGNN_OK;
-  const int tiles = (a.M + C::TM - 1) / C::TM + (a.grp_ptr ? a.S : 0);
-  static bool attr_set = false;
-  if (!attr_set) {
-    HGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<H, BF16>),
-                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES));
-    attr_set = true;
+// workgroups of this variant that one CU holds at a time (asked once; also raises the LDS limit of the kernel)
+template <int H, bool BF16, int TM>
+static int gemm_resident_wgs() {
+  using C = GemmCfg<H, BF16, TM>;
+  static int n = 0;
+  if (n == 0) {
+    const void* fn = reinterpret_cast<const void*>(&k_gemm<H, BF16, TM>);
+    int occ = 0;
+    if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES) != hipSuccess ||
+        hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, fn, 256, C::LDS_BYTES) != hipSuccess || occ < 1)
+      occ = 1;
+    n = occ;
   }
+  return n;
+}
+
+template <int H, bool BF16, int TM>
+static int32_t launch_gemm_tm(hipStream_t st, const GemmArgs& a) {
+  using C = GemmCfg<H, BF16, TM>;
+  const int tiles = (a.M + C::TM - 1) / C::TM + (a.grp_ptr ? a.S : 0);
+  gemm_resident_wgs<H, BF16, TM>();
   ProfScope ps(a.tag, st);
-  k_gemm<H, BF16><<<dim3(tiles, a.ncb), 256, C::LDS_BYTES, st>>>(a);
+  k_gemm<H, BF16, TM><<<dim3(tiles, a.ncb), 256, C::LDS_BYTES, st>>>(a);
   HGNN_LAUNCH_CHECK("k_gemm");
   return HGNN_OK;
+}
+
+// Every tile costs about the same, so a launch takes ceil(workgroups / resident workgroups) rounds of a duration
+// that grows with the tile height: take the height with the fewest row-rounds (ties: the taller tile, which
+// stages and re-reads less).
+template <int H, bool BF16>
+static int32_t launch_gemm_t(hipStream_t st, const GemmArgs& a) {
+  if (a.M <= 0) return HGNN_OK;
+  // 96 rows need every wavefront to span the whole tile height, and two such tiles must still fit one CU's LDS
+  constexpr size_t lds96 = (size_t)96 * GemmCfg<H, BF16>::STRIDE * (BF16 ? 2 : 4);
+  if constexpr (GemmCfg<H, BF16>::WR == 1 && 2 * lds96 <= 160 * 1024) {
+    auto row_rounds = [&](int tm, int resident) {
+      const long slots = (long)resident * num_cus();
+      const long wgs = ((long)(a.M + tm - 1) / tm + (a.grp_ptr ? a.S : 0)) * a.ncb;
+      return (wgs + slots - 1) / slots * tm;
+    };
+    if (row_rounds(96, gemm_resident_wgs<H, BF16, 96>()) <= row_rounds(64, gemm_resident_wgs<H, BF16, 64>()))
+      return launch_gemm_tm<H, BF16, 96>(st, a);
+  }
+  return launch_gemm_tm<H, BF16, 64>(st, a);
 }
 
 int32_t launch_gemm(hipStream_t st, int H, bool bf16, const GemmArgs& a) {

@@ -6,6 +6,8 @@
 // gathers and adds two rows. The per-edge matrix work is then the single H x H product with W2.
 // The reverse pass mirrors this: the gradient with respect to z1 is reduced per destination (g_P)
 // and per source (g_Q, through the source-sorted plan) and the W1 products run per atom again.
+#include <cstdlib>
+
 #include "edge_fused.h"
 #include "edgeops.h"
 #include "gemm.h"
@@ -246,7 +248,9 @@ extern "C" int32_t hgnn_mp_layer_bwd(void* stream, int32_t N, int64_t E, int32_t
 
   SideStream& ss = side_stream();
   HGNN_REQUIRE(ss.ok, HGNN_ERR_HIP, "could not create the side stream");
-  hipStream_t sx = ss.s;
+  // HGNN_SIDE_STREAM=0 keeps everything on the caller's stream (for timing kernels in isolation)
+  static const bool use_side = [] { const char* e = getenv("HGNN_SIDE_STREAM"); return !(e && e[0] == '0'); }();
+  hipStream_t sx = use_side ? ss.s : st;
   HGNN_TRY(stream_after(sx, st, ss.ev[0]));   // inputs of this call are ready on the side stream too
 
   // every gradient field is written below even when there is nothing to sum over
@@ -295,8 +299,10 @@ extern "C" int32_t hgnn_mp_layer_bwd(void* stream, int32_t N, int64_t E, int32_t
     }
     HGNN_TRY(launch_gemm(st, H, bf16, g));
   }
-  // edge part: c_e, then g_z2 -> (x W2^T) -> g_z1 with the per-column sums
+  // edge part: c_e, then g_z2 -> (x W2^T) -> g_z1 with the per-column sums. The fused edge kernel fills
+  // every CU by itself, so the side stream is drained first instead of competing with it.
   HGNN_TRY(launch_edge_cvec(st, E, dst, rvec, g_v_out, alpha, w.cvec));
+  HGNN_TRY(stream_after(st, sx, ss.ev[5]));
   {
     EdgeBwdArgs e;
     e.E = E; e.dst = dst; e.col = col; e.d2 = d2;
