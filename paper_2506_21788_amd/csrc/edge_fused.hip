@@ -16,6 +16,9 @@
 
 namespace hgnn {
 
+// largest edge count the 32-bit edge indices of these kernels reach (a whole tile beyond E must still fit)
+constexpr int64_t EDGE_MAX_E = 2147483647LL - 128;
+
 template <int H, bool BF16>
 struct ECfg {
   static constexpr int TM = 64;                       // edges per tile
@@ -50,6 +53,23 @@ __device__ __forceinline__ void load4(const float* __restrict__ p, int64_t e4, i
   }
 }
 
+// Streaming accesses are written as (uniform 64-bit base) + (32-bit per-lane byte offset): the base lives in scalar
+// registers, the lane part is one register shared by every access, and constant strides fold into the instruction.
+template <typename T>
+__device__ __forceinline__ T ldg_nt(const void* ubase, unsigned off) {
+  return __builtin_nontemporal_load(reinterpret_cast<const T*>(reinterpret_cast<const char*>(ubase) + off));
+}
+template <typename T>
+__device__ __forceinline__ T ldg_at(const void* ubase, unsigned off) {
+  return *reinterpret_cast<const T*>(reinterpret_cast<const char*>(ubase) + off);
+}
+template <typename T>
+__device__ __forceinline__ void stg_nt(void* ubase, unsigned off, T v) {
+  __builtin_nontemporal_store(v, reinterpret_cast<T*>(reinterpret_cast<char*>(ubase) + off));
+}
+__device__ __forceinline__ const char* uoff(const void* base, size_t bytes) { return reinterpret_cast<const char*>(base) + bytes; }
+__device__ __forceinline__ char* uoff(void* base, size_t bytes) { return reinterpret_cast<char*>(base) + bytes; }
+
 // 8 accumulator-mapped values of one half of a 32x32 block (column n of the tile, registers v = 8*vh .. 8*vh+7,
 // rows rbase + 8*(v>>2) + 4g + (v&3)): written row-major into the LDS tile and, operand-packed, to memory.
 // bf16 values are converted once.
@@ -69,17 +89,17 @@ __device__ __forceinline__ void emit_half(unsigned char* smem, int rbase, int g,
     {
       typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
       const u32x4_t w = {pk[0], pk[1], pk[2], pk[3]};
-      __builtin_nontemporal_store(w, reinterpret_cast<u32x4_t*>(packed) + (blk * 2 + vh) * 64 + lane);
+      stg_nt<u32x4_t>(uoff(packed, (blk * 2 + vh) * 1024), lane * 16u, w);
     }
   } else {
     float* s32 = reinterpret_cast<float*>(smem);
 #pragma unroll
     for (int u = 0; u < 8; ++u) s32[(rbase + 8 * (2 * vh + (u >> 2)) + 4 * g + (u & 3)) * STRIDE + n] = vals[u];
-    f32x4_t* p = reinterpret_cast<f32x4_t*>(packed) + (blk * 4 + 2 * vh) * 64 + lane;
+    char* pb = uoff(packed, (blk * 4 + 2 * vh) * 1024);
     const f32x4_t w0 = {vals[0], vals[1], vals[2], vals[3]};
     const f32x4_t w1 = {vals[4], vals[5], vals[6], vals[7]};
-    __builtin_nontemporal_store(w0, p);
-    __builtin_nontemporal_store(w1, p + 64);
+    stg_nt<f32x4_t>(pb, lane * 16u, w0);
+    stg_nt<f32x4_t>(pb, lane * 16u + 1024u, w1);
   }
 }
 
@@ -104,7 +124,6 @@ __device__ __forceinline__ void tile_mma(const unsigned char* smem, const void* 
                                          f32x16_t (&acc)[ECfg<H, BF16>::RB][ECfg<H, BF16>::CB]) {
   using C = ECfg<H, BF16>;
   if (BF16) {
-    const bf16x8_t* __restrict__ Bp = reinterpret_cast<const bf16x8_t*>(Bpacked);
     constexpr int NKB = H / 16;
 #pragma unroll 4
     for (int kb = 0; kb < NKB; ++kb) {
@@ -116,13 +135,12 @@ __device__ __forceinline__ void tile_mma(const unsigned char* smem, const void* 
       }
 #pragma unroll
       for (int j = 0; j < C::CB; ++j) {
-        const bf16x8_t b = Bp[((wc * C::CB + j) * NKB + kb) * 64 + lane];
+        const bf16x8_t b = ldg_at<bf16x8_t>(uoff(Bpacked, (size_t)((wc * C::CB + j) * NKB + kb) * 1024), lane * 16u);
 #pragma unroll
         for (int i = 0; i < C::RB; ++i) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b, acc[i][j], 0, 0, 0);
       }
     }
   } else {
-    const float4* __restrict__ Bp = reinterpret_cast<const float4*>(Bpacked);
     constexpr int NKB = H / 8;
 #pragma unroll 4
     for (int kb = 0; kb < NKB; ++kb) {
@@ -134,7 +152,7 @@ __device__ __forceinline__ void tile_mma(const unsigned char* smem, const void* 
       }
 #pragma unroll
       for (int j = 0; j < C::CB; ++j) {
-        const float4 b = Bp[((wc * C::CB + j) * NKB + kb) * 64 + lane];
+        const float4 b = ldg_at<float4>(uoff(Bpacked, (size_t)((wc * C::CB + j) * NKB + kb) * 1024), lane * 16u);
 #pragma unroll
         for (int i = 0; i < C::RB; ++i) {
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].x, b.x, acc[i][j], 0, 0, 0);
@@ -212,32 +230,54 @@ __device__ __forceinline__ void tile_mma_res(const unsigned char* smem, int wr, 
   }
 }
 
-// Per-edge scalars of a tile (dst | col | d2 bits), fetched one tile ahead into LDS: element tid of [3][TM]
-template <int TM>
+// Per-edge scalars of a tile, fetched one tile ahead into LDS: element tid of [NARR][TM] with arrays
+// dst | col | d2 bits (| c bits); zeros beyond the last edge (row 0 is always a valid row to gather)
+template <int TM, int NARR>
 __device__ __forceinline__ int fetch_edge_scalar(const int32_t* __restrict__ dst, const int32_t* __restrict__ col,
-                                                 const float* __restrict__ d2, int tile, int tile_end, int64_t E,
-                                                 int tid) {
+                                                 const float* __restrict__ d2, const float* __restrict__ cvec, int tile,
+                                                 int tile_end, int E, int tid) {
   const int which = tid / TM, r = tid - which * TM;
-  const int64_t e = (int64_t)tile * TM + r;
-  if (tid >= 3 * TM || tile >= tile_end || e >= E) return 0;
-  return which == 0 ? dst[e] : (which == 1 ? col[e] : __float_as_int(d2[e]));
+  const int e = tile * TM + r;
+  if (which >= NARR || tile >= tile_end || e >= E) return 0;
+  switch (which) {
+    case 0: return dst[e];
+    case 1: return col[e];
+    case 2: return __float_as_int(d2[e]);
+    default: return __float_as_int(cvec[e]);
+  }
 }
 
-// z1 = P[dst] + Q[col] + d2*w1d for 8 edges and this lane's CB column blocks.
+// Loads at a 32-bit byte offset from a uniform base: one address register per lane and no 64-bit arithmetic.
+// (The host checks that every gathered node tensor is smaller than 4 GiB.)
+__device__ __forceinline__ unsigned ldg_u32(const void* base, unsigned byte_off) {
+  return *reinterpret_cast<const unsigned*>(reinterpret_cast<const char*>(base) + byte_off);
+}
+__device__ __forceinline__ float ldg_f32(const void* base, unsigned byte_off) {
+  return *reinterpret_cast<const float*>(reinterpret_cast<const char*>(base) + byte_off);
+}
+
+// Row pitch in bytes of the projected features [P | Q]: H words of bf16 pairs, or 2H floats
+template <int H, bool PAIRS>
+struct PQPitch {
+  static constexpr unsigned ROW = PAIRS ? H * 4u : 2u * H * 4u;
+  static constexpr unsigned QOFF = PAIRS ? H * 2u : H * 4u;   // byte offset of the Q half inside a row
+};
+
+// z1 = P[dst] + Q[col] + d2*w1d for 8 edges and this lane's CB column blocks. colb = byte offset of this
+// lane's first column inside the P half of a row.
 // PAIRS: the projected features are stored as bf16 pairs, one 32-bit word holding this lane's two
 // columns (block 2*wc and block 2*wc+1) of P or Q; a row is [H/2 words of P | H/2 words of Q].
 template <int H, int CB, bool PAIRS>
 __device__ __forceinline__ void gather_z1(const void* __restrict__ PQ, const int* di, const int* ci, const float* dd,
-                                          const float* w1d, int wc, int x, float (&z)[CB][8]) {
+                                          const float* w1d, unsigned colb, float (&z)[CB][8]) {
+  using P = PQPitch<H, PAIRS>;
   if constexpr (PAIRS) {
     static_assert(CB == 2, "pair storage needs two column blocks per lane");
-    const unsigned* __restrict__ U = reinterpret_cast<const unsigned*>(PQ);
-    const int wcol = wc * 32 + x;
     unsigned wp[8], wq[8];
 #pragma unroll
     for (int u = 0; u < 8; ++u) {
-      wp[u] = U[di[u] * H + wcol];
-      wq[u] = U[ci[u] * H + (H / 2) + wcol];
+      wp[u] = ldg_u32(PQ, (unsigned)di[u] * P::ROW + colb);
+      wq[u] = ldg_u32(PQ, (unsigned)ci[u] * P::ROW + colb + P::QOFF);
     }
 #pragma unroll
     for (int u = 0; u < 8; ++u) {
@@ -245,15 +285,13 @@ __device__ __forceinline__ void gather_z1(const void* __restrict__ PQ, const int
       z[1][u] = __uint_as_float(wp[u] & 0xffff0000u) + __uint_as_float(wq[u] & 0xffff0000u) + dd[u] * w1d[1];
     }
   } else {
-    const float* __restrict__ F = reinterpret_cast<const float*>(PQ);
 #pragma unroll
     for (int j = 0; j < CB; ++j) {
-      const int n = (wc * CB + j) * 32 + x;
       float a[8], b[8];
 #pragma unroll
       for (int u = 0; u < 8; ++u) {
-        a[u] = F[di[u] * 2 * H + n];
-        b[u] = F[ci[u] * 2 * H + H + n];
+        a[u] = ldg_f32(PQ, (unsigned)di[u] * P::ROW + colb + j * 128u);
+        b[u] = ldg_f32(PQ, (unsigned)ci[u] * P::ROW + colb + j * 128u + P::QOFF);
       }
 #pragma unroll
       for (int u = 0; u < 8; ++u) z[j][u] = a[u] + b[u] + dd[u] * w1d[j];
@@ -269,21 +307,120 @@ __device__ __forceinline__ void lds_rows8(const int* s, int rblk, int vh, int g,
     o[4 * jj + 0] = t.x; o[4 * jj + 1] = t.y; o[4 * jj + 2] = t.z; o[4 * jj + 3] = t.w;
   }
 }
+__device__ __forceinline__ void lds_rows8(const int* s, int rblk, int vh, int g, float* o) {
+#pragma unroll
+  for (int jj = 0; jj < 2; ++jj) {
+    const float4 t = *reinterpret_cast<const float4*>(s + rblk * 32 + 8 * (2 * vh + jj) + 4 * g);
+    o[4 * jj + 0] = t.x; o[4 * jj + 1] = t.y; o[4 * jj + 2] = t.z; o[4 * jj + 3] = t.w;
+  }
+}
+// bit u set <=> edge eb*32 + 8*(2*vh + (u>>2)) + 4*g + (u&3) exists
+__device__ __forceinline__ unsigned rows8_mask(int eb, int vh, int g, int E) {
+  unsigned ok = 0;
+#pragma unroll
+  for (int u = 0; u < 8; ++u) ok |= (eb * 32 + 8 * (2 * vh + (u >> 2)) + 4 * g + (u & 3) < E ? 1u : 0u) << u;
+  return ok;
+}
 
 // ---------------------------------------------------------------------------------------------
 // forward
 // ---------------------------------------------------------------------------------------------
+// One tile of the forward kernel. FULL: all TM edges of the tile exist (no masking anywhere).
+template <int H, bool BF16, bool BRES, bool FULL>
+__device__ __forceinline__ void edge_fwd_tile(
+    const EdgeFwdArgs& p, unsigned char* smem, const int* s, int* s_next, int nxt, int tile, int E, int tid, int wr,
+    int wc, int lane, const float (&w1d)[ECfg<H, BF16>::CB], const float (&b2)[ECfg<H, BF16>::CB],
+    const typename BFrag<H, BF16>::type (&breg)[BRES ? BFrag<H, BF16>::NKB : 1][ECfg<H, BF16>::CB]) {
+  using C = ECfg<H, BF16>;
+  constexpr bool PAIRS = BF16 && C::CB == 2;
+  const int g = lane >> 5, x = lane & 31;
+  // byte offset of this lane's first column inside a row: word wc*32 + x of bf16 pairs, else column wc*CB*32 + x
+  const unsigned colb = (unsigned)((PAIRS ? wc * 32 : wc * C::CB * 32) + x) * 4u;
+  // ---- produce a1 for this wavefront's blocks: memory (operand-packed) and LDS (row-major)
+#pragma unroll
+  for (int i = 0; i < C::RB; ++i) {
+    const int rblk = wr * C::RB + i;
+    const int eb = tile * (C::TM / 32) + rblk;
+    if (!FULL && eb * 32 >= E) continue;
+#pragma unroll
+    for (int vh = 0; vh < 2; ++vh) {
+      int di[8], ci[8];
+      float dd[8];
+      lds_rows8(s, rblk, vh, g, di);
+      lds_rows8(s + C::TM, rblk, vh, g, ci);
+      lds_rows8(s + 2 * C::TM, rblk, vh, g, dd);
+      const unsigned ok = FULL ? 0xffu : rows8_mask(eb, vh, g, E);
+      float z[C::CB][8];
+      gather_z1<H, C::CB, PAIRS>(p.PQ, di, ci, dd, w1d, colb, z);
+#pragma unroll
+      for (int j = 0; j < C::CB; ++j) {
+        const int cblk = wc * C::CB + j;
+        const int n = cblk * 32 + x;
+        float vals[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          vals[u] = silu_f(z[j][u]);
+          if (!FULL && !((ok >> u) & 1u)) vals[u] = 0.f;
+        }
+        emit_half<BF16, C::STRIDE>(smem, rblk * 32, g, n, vals, vh, p.a1_pk, (size_t)eb * C::NCB + cblk, lane);
+      }
+    }
+  }
+  __syncthreads();
+  f32x16_t acc[C::RB][C::CB];
+#pragma unroll
+  for (int i = 0; i < C::RB; ++i)
+#pragma unroll
+    for (int j = 0; j < C::CB; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+  if constexpr (BRES) tile_mma_res<H, BF16>(smem, wr, lane, breg, acc);
+  else tile_mma<H, BF16>(smem, p.W2p, wr, wc, lane, acc);
+  if (tid < 3 * C::TM) s_next[tid] = nxt;
+  __syncthreads();
+  // ---- z2 = acc + b2, stored v-major (as bf16 pairs of this lane's two column blocks when PAIRS)
+#pragma unroll
+  for (int i = 0; i < C::RB; ++i) {
+    const int eb = tile * (C::TM / 32) + wr * C::RB + i;
+    if (!FULL && eb * 32 >= E) continue;
+    if constexpr (PAIRS) {
+      char* o = uoff(p.z2_vm, ((size_t)eb * (C::NCB / 2) + wc) * 16 * 256);
+#pragma unroll
+      for (int v = 0; v < 16; ++v)
+        stg_nt<unsigned>(o, lane * 4u + v * 256u, pack_bf16x2(acc[i][0][v] + b2[0], acc[i][1][v] + b2[1]));
+    } else {
+#pragma unroll
+      for (int j = 0; j < C::CB; ++j) {
+        const size_t blk = ((size_t)eb * C::NCB + (wc * C::CB + j)) * 16 * 64;   // first element of the block
+        if (BF16) {
+          char* o = uoff(p.z2_vm, blk * 2);
+#pragma unroll
+          for (int t = 0; t < 8; ++t) {
+            const unsigned pk = pack_bf16x2(acc[i][j][2 * t] + b2[j], acc[i][j][2 * t + 1] + b2[j]);
+            stg_nt<unsigned short>(o, lane * 2u + (2 * t) * 128u, (unsigned short)(pk & 0xffffu));
+            stg_nt<unsigned short>(o, lane * 2u + (2 * t + 1) * 128u, (unsigned short)(pk >> 16));
+          }
+        } else {
+          char* o = uoff(p.z2_vm, blk * 4);
+#pragma unroll
+          for (int v = 0; v < 16; ++v) stg_nt<float>(o, lane * 4u + v * 256u, acc[i][j][v] + b2[j]);
+        }
+      }
+    }
+  }
+}
+
 template <int H, bool BF16, bool BRES_REQ>
-__global__ void __launch_bounds__(256, BRES_REQ ? 2 : 3) k_edge_fwd(EdgeFwdArgs p, int ntiles) {
+__global__ void __launch_bounds__(256, 2) k_edge_fwd(EdgeFwdArgs p, int ntiles) {
   using C = ECfg<H, BF16>;
   constexpr bool BRES = BRES_REQ && (BF16 || H <= 128);   // keep this wavefront's slice of W2 in registers?
-  constexpr bool PAIRS = BF16 && C::CB == 2;
   extern __shared__ __align__(16) unsigned char smem[];
   int* sc = reinterpret_cast<int*>(smem + C::LDS_BYTES);   // [2][3][TM] per-edge scalars, double buffered
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: tile addresses stay in scalar registers
   const int wr = wave / C::WC, wc = wave % C::WC;
-  const int g = lane >> 5, x = lane & 31;
-  const int64_t E = p.E;
+  const int x = lane & 31;
+  const int E = (int)p.E;
   float w1d[C::CB], b2[C::CB];
 #pragma unroll
   for (int j = 0; j < C::CB; ++j) {
@@ -295,90 +432,20 @@ __global__ void __launch_bounds__(256, BRES_REQ ? 2 : 3) k_edge_fwd(EdgeFwdArgs 
   if constexpr (BRES) load_b_resident<H, BF16>(p.W2p, wc, lane, breg);
   const TileRange tr = xcd_tile_range(ntiles);
   {
-    const int s0 = fetch_edge_scalar<C::TM>(p.dst, p.col, p.d2, tr.first, tr.end, E, tid);
+    const int s0 = fetch_edge_scalar<C::TM, 3>(p.dst, p.col, p.d2, nullptr, tr.first, tr.end, E, tid);
     if (tid < 3 * C::TM) sc[tid] = s0;
   }
   __syncthreads();
   int buf = 0;
   for (int tile = tr.first; tile < tr.end; tile += tr.step, buf ^= 1) {
     // the next tile's scalars travel while this tile is processed
-    const int nxt = fetch_edge_scalar<C::TM>(p.dst, p.col, p.d2, tile + tr.step, tr.end, E, tid);
+    const int nxt = fetch_edge_scalar<C::TM, 3>(p.dst, p.col, p.d2, nullptr, tile + tr.step, tr.end, E, tid);
     const int* s = sc + buf * 3 * C::TM;
-    // ---- produce a1 for this wavefront's blocks: memory (operand-packed) and LDS (row-major)
-#pragma unroll
-    for (int i = 0; i < C::RB; ++i) {
-      const int rblk = wr * C::RB + i;
-      const int64_t eb = (int64_t)tile * (C::TM / 32) + rblk;
-      if (eb * 32 >= E) continue;
-#pragma unroll
-      for (int vh = 0; vh < 2; ++vh) {
-        int di[8], ci[8], dbits[8];
-        float dd[8];
-        lds_rows8(s, rblk, vh, g, di);
-        lds_rows8(s + C::TM, rblk, vh, g, ci);
-        lds_rows8(s + 2 * C::TM, rblk, vh, g, dbits);
-        unsigned ok = 0;
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-          dd[u] = __int_as_float(dbits[u]);
-          const int64_t e = eb * 32 + 8 * (2 * vh + (u >> 2)) + 4 * g + (u & 3);
-          ok |= (e < E ? 1u : 0u) << u;
-        }
-        float z[C::CB][8];
-        gather_z1<H, C::CB, PAIRS>(p.PQ, di, ci, dd, w1d, wc, x, z);
-#pragma unroll
-        for (int j = 0; j < C::CB; ++j) {
-          const int cblk = wc * C::CB + j;
-          const int n = cblk * 32 + x;
-          float vals[8];
-#pragma unroll
-          for (int u = 0; u < 8; ++u) vals[u] = ((ok >> u) & 1u) ? silu_f(z[j][u]) : 0.f;
-          emit_half<BF16, C::STRIDE>(smem, rblk * 32, g, n, vals, vh, p.a1_pk, (size_t)eb * C::NCB + cblk, lane);
-        }
-      }
-    }
-    __syncthreads();
-    f32x16_t acc[C::RB][C::CB];
-#pragma unroll
-    for (int i = 0; i < C::RB; ++i)
-#pragma unroll
-      for (int j = 0; j < C::CB; ++j)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-    if constexpr (BRES) tile_mma_res<H, BF16>(smem, wr, lane, breg, acc);
-    else tile_mma<H, BF16>(smem, p.W2p, wr, wc, lane, acc);
-    if (tid < 3 * C::TM) sc[(buf ^ 1) * 3 * C::TM + tid] = nxt;
-    __syncthreads();
-    // ---- z2 = acc + b2, stored v-major (as bf16 pairs of this lane's two column blocks when PAIRS)
-#pragma unroll
-    for (int i = 0; i < C::RB; ++i) {
-      const int64_t eb = (int64_t)tile * (C::TM / 32) + wr * C::RB + i;
-      if (eb * 32 >= E) continue;
-      if constexpr (PAIRS) {
-        unsigned* o = reinterpret_cast<unsigned*>(p.z2_vm) + (((size_t)eb * (C::NCB / 2) + wc) * 16) * 64 + lane;
-#pragma unroll
-        for (int v = 0; v < 16; ++v)
-          __builtin_nontemporal_store(pack_bf16x2(acc[i][0][v] + b2[0], acc[i][1][v] + b2[1]), o + v * 64);
-      } else {
-#pragma unroll
-        for (int j = 0; j < C::CB; ++j) {
-          const size_t base = (((size_t)eb * C::NCB + (wc * C::CB + j)) * 16) * 64 + lane;
-          if (BF16) {
-            unsigned short* o = reinterpret_cast<unsigned short*>(p.z2_vm) + base;
-#pragma unroll
-            for (int t = 0; t < 8; ++t) {
-              const unsigned pk = pack_bf16x2(acc[i][j][2 * t] + b2[j], acc[i][j][2 * t + 1] + b2[j]);
-              __builtin_nontemporal_store((unsigned short)(pk & 0xffffu), o + (2 * t) * 64);
-              __builtin_nontemporal_store((unsigned short)(pk >> 16), o + (2 * t + 1) * 64);
-            }
-          } else {
-            float* o = reinterpret_cast<float*>(p.z2_vm) + base;
-#pragma unroll
-            for (int v = 0; v < 16; ++v) __builtin_nontemporal_store(acc[i][j][v] + b2[j], o + v * 64);
-          }
-        }
-      }
-    }
+    int* s_next = sc + (buf ^ 1) * 3 * C::TM;
+    if ((tile + 1) * C::TM <= E)
+      edge_fwd_tile<H, BF16, BRES, true>(p, smem, s, s_next, nxt, tile, E, tid, wr, wc, lane, w1d, b2, breg);
+    else
+      edge_fwd_tile<H, BF16, BRES, false>(p, smem, s, s_next, nxt, tile, E, tid, wr, wc, lane, w1d, b2, breg);
   }
 }
 
@@ -391,21 +458,19 @@ static int32_t launch_edge_fwd_t(hipStream_t st, const EdgeFwdArgs& a) {
   if (!attr_set) {
     HGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_edge_fwd<H, BF16, true>),
                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)(C::LDS_BYTES + 6 * C::TM * 4)));
-    HGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_edge_fwd<H, BF16, false>),
-                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)(C::LDS_BYTES + 6 * C::TM * 4)));
     attr_set = true;
   }
-  static const bool bres = [] { const char* e = getenv("HGNN_BRES"); return !(e && e[0] == '0'); }();
-  int64_t grid = (int64_t)num_cus() * (bres ? 4 : 3);
+  int64_t grid = (int64_t)num_cus() * 4;
   if (grid > ntiles) grid = ntiles;
   ProfScope ps(PT_EDGE_FUSED_FWD, st);
-  if (bres) k_edge_fwd<H, BF16, true><<<dim3((unsigned)grid), 256, C::LDS_BYTES + 6 * C::TM * 4, st>>>(a, (int)ntiles);
-  else k_edge_fwd<H, BF16, false><<<dim3((unsigned)grid), 256, C::LDS_BYTES + 6 * C::TM * 4, st>>>(a, (int)ntiles);
+  k_edge_fwd<H, BF16, true><<<dim3((unsigned)grid), 256, C::LDS_BYTES + 6 * C::TM * 4, st>>>(a, (int)ntiles);
   HGNN_LAUNCH_CHECK("k_edge_fwd");
   return HGNN_OK;
 }
 
 int32_t launch_edge_fwd(hipStream_t st, int H, bool bf16, const EdgeFwdArgs& a) {
+  HGNN_REQUIRE(a.E >= 0 && a.E <= EDGE_MAX_E, HGNN_ERR_BAD_SHAPE, "edge kernels index edges with 32 bits (E = %lld)",
+               (long long)a.E);
   switch (H) {
     case 64: return bf16 ? launch_edge_fwd_t<64, true>(st, a) : launch_edge_fwd_t<64, false>(st, a);
     case 128: return bf16 ? launch_edge_fwd_t<128, true>(st, a) : launch_edge_fwd_t<128, false>(st, a);
@@ -602,15 +667,157 @@ int32_t launch_edge_cvec(hipStream_t st, int64_t E, const int32_t* dst, const fl
   return HGNN_OK;
 }
 
+// One tile of the reverse kernel. FULL: all TM edges of the tile exist (no masking anywhere).
+template <int H, bool BF16, bool FULL>
+__device__ __forceinline__ void edge_bwd_tile(const EdgeBwdArgs& p, unsigned char* smem, const int* s, int* s_next,
+                                              int nxt, int tile, int E, int tid, int wr, int wc, int lane,
+                                              const float (&w1d)[ECfg<H, BF16>::CB], const float (&wxn)[ECfg<H, BF16>::CB],
+                                              float (&sb2)[ECfg<H, BF16>::CB], float (&swx)[ECfg<H, BF16>::CB],
+                                              float (&sw1)[ECfg<H, BF16>::CB]) {
+  using C = ECfg<H, BF16>;
+  constexpr bool PAIRS = BF16 && C::CB == 2;
+  constexpr unsigned GM_ROW = PAIRS ? H * 2u : 2u * H * 4u;   // row pitch of g_M in bytes (checked by the launcher)
+  const int g = lane >> 5, x = lane & 31;
+  // byte offset of this lane's first column inside a row: word wc*32 + x of bf16 pairs, else column wc*CB*32 + x
+  const unsigned colb = (unsigned)((PAIRS ? wc * 32 : wc * C::CB * 32) + x) * 4u;
+  // ---- g_z2 = (alpha*g_M[dst] + c*wx) * silu'(z2): operand-packed to memory, row-major to LDS
+#pragma unroll
+  for (int i = 0; i < C::RB; ++i) {
+    const int rblk = wr * C::RB + i;
+    const int eb = tile * (C::TM / 32) + rblk;
+    if (!FULL && eb * 32 >= E) continue;
+#pragma unroll
+    for (int vh = 0; vh < 2; ++vh) {
+      int di[8];
+      float cc[8];
+      lds_rows8(s, rblk, vh, g, di);
+      lds_rows8(s + 3 * C::TM, rblk, vh, g, cc);
+      const unsigned ok = FULL ? 0xffu : rows8_mask(eb, vh, g, E);
+      float gm[C::CB][8];
+      unsigned zw[8];   // PAIRS: z2 of both column blocks, one word per edge
+      if constexpr (PAIRS) {
+        const char* zp = uoff(p.z2_vm, (((size_t)eb * (C::NCB / 2) + wc) * 16 + 8 * vh) * 256);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) zw[u] = ldg_nt<unsigned>(zp, lane * 4u + u * 256u);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const unsigned w = ldg_u32(p.gM, (unsigned)di[u] * GM_ROW + colb);
+          gm[0][u] = __uint_as_float(w << 16);
+          gm[1][u] = __uint_as_float(w & 0xffff0000u);
+        }
+      } else {
+#pragma unroll
+        for (int j = 0; j < C::CB; ++j)
+#pragma unroll
+          for (int u = 0; u < 8; ++u) gm[j][u] = ldg_f32(p.gM, (unsigned)di[u] * GM_ROW + colb + j * 128u);
+      }
+#pragma unroll
+      for (int j = 0; j < C::CB; ++j) {
+        const int cblk = wc * C::CB + j;
+        const int n = cblk * 32 + x;
+        const size_t zblk = (((size_t)eb * C::NCB + cblk) * 16 + 8 * vh) * 64;   // first element of the half block
+        float zz[8], vals[8];
+        if constexpr (PAIRS) {
+#pragma unroll
+          for (int u = 0; u < 8; ++u) zz[u] = j == 0 ? __uint_as_float(zw[u] << 16) : __uint_as_float(zw[u] & 0xffff0000u);
+        } else {
+#pragma unroll
+          for (int u = 0; u < 8; ++u)
+            zz[u] = BF16 ? bf_bits_to_f(ldg_nt<unsigned short>(uoff(p.z2_vm, zblk * 2), lane * 2u + u * 128u))
+                         : ldg_nt<float>(uoff(p.z2_vm, zblk * 4), lane * 4u + u * 256u);
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          float m, dm;
+          silu_both(zz[u], m, dm);
+          float gz = (p.alpha * gm[j][u] + cc[u] * wxn[j]) * dm;
+          if (!FULL && !((ok >> u) & 1u)) gz = 0.f;   // c is zero there, so the wx sum needs no mask
+          vals[u] = gz;
+          sb2[j] += gz;
+          swx[j] += cc[u] * m;
+        }
+        emit_half<BF16, C::STRIDE>(smem, rblk * 32, g, n, vals, vh, p.gz2_pk, (size_t)eb * C::NCB + cblk, lane);
+      }
+      // the running column sums are complete for this group here: without this the compiler defers their chains
+      // past the matrix product and keeps every operand alive (in scratch memory) until then
+#pragma unroll
+      for (int j = 0; j < C::CB; ++j) asm volatile("" : "+v"(sb2[j]), "+v"(swx[j]));
+    }
+  }
+  __syncthreads();
+  f32x16_t acc[C::RB][C::CB];
+#pragma unroll
+  for (int i = 0; i < C::RB; ++i)
+#pragma unroll
+    for (int j = 0; j < C::CB; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+  tile_mma<H, BF16>(smem, p.W2Tp, wr, wc, lane, acc);
+  s_next[tid] = nxt;
+  __syncthreads();
+  // ---- g_z1 = g_a1 * silu'(z1), z1 recomputed from the projected node features
+#pragma unroll
+  for (int i = 0; i < C::RB; ++i) {
+    const int rblk = wr * C::RB + i;
+    const int eb = tile * (C::TM / 32) + rblk;
+    if (!FULL && eb * 32 >= E) continue;
+#pragma unroll
+    for (int vh = 0; vh < 2; ++vh) {
+      int di[8], ci[8];
+      float dd[8];
+      lds_rows8(s, rblk, vh, g, di);
+      lds_rows8(s + C::TM, rblk, vh, g, ci);
+      lds_rows8(s + 2 * C::TM, rblk, vh, g, dd);
+      float z[C::CB][8];
+      gather_z1<H, C::CB, PAIRS>(p.PQ, di, ci, dd, w1d, colb, z);
+      float gv[C::CB][8];
+#pragma unroll
+      for (int j = 0; j < C::CB; ++j)
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          gv[j][u] = acc[i][j][8 * vh + u] * dsilu_f(z[j][u]);   // rows beyond E have acc == 0
+          sw1[j] += dd[u] * gv[j][u];
+        }
+      if constexpr (PAIRS) {
+        char* o = uoff(p.gz1_vm, (((size_t)eb * (C::NCB / 2) + wc) * 16 + 8 * vh) * 256);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) stg_nt<unsigned>(o, lane * 4u + u * 256u, pack_bf16x2(gv[0][u], gv[1][u]));
+      } else {
+#pragma unroll
+        for (int j = 0; j < C::CB; ++j) {
+          const size_t blk = (((size_t)eb * C::NCB + (wc * C::CB + j)) * 16 + 8 * vh) * 64;
+          if constexpr (BF16) {
+            char* o = uoff(p.gz1_vm, blk * 2);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+              const unsigned pk = pack_bf16x2(gv[j][2 * t], gv[j][2 * t + 1]);
+              stg_nt<unsigned short>(o, lane * 2u + (2 * t) * 128u, (unsigned short)(pk & 0xffffu));
+              stg_nt<unsigned short>(o, lane * 2u + (2 * t + 1) * 128u, (unsigned short)(pk >> 16));
+            }
+          } else {
+            char* o = uoff(p.gz1_vm, blk * 4);
+#pragma unroll
+            for (int u = 0; u < 8; ++u) stg_nt<float>(o, lane * 4u + u * 256u, gv[j][u]);
+          }
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < C::CB; ++j) asm volatile("" : "+v"(sw1[j]));
+    }
+  }
+}
+
 template <int H, bool BF16>
 __global__ void __launch_bounds__(256, 3) k_edge_bwd(EdgeBwdArgs p, int ntiles) {
   using C = ECfg<H, BF16>;
-  constexpr bool PAIRS = BF16 && C::CB == 2;
   extern __shared__ __align__(16) unsigned char smem[];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  int* sc = reinterpret_cast<int*>(smem + C::LDS_BYTES);   // [2][4][TM] per-edge scalars dst|col|d2|c, double buffered
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: tile addresses stay in scalar registers
   const int wr = wave / C::WC, wc = wave % C::WC;
   const int g = lane >> 5, x = lane & 31;
-  const int64_t E = p.E;
+  const int E = (int)p.E;
+  static_assert(4 * C::TM == 256, "one per-edge scalar per thread");
   float w1d[C::CB], wxn[C::CB], sb2[C::CB], swx[C::CB], sw1[C::CB];
 #pragma unroll
   for (int j = 0; j < C::CB; ++j) {
@@ -620,136 +827,18 @@ __global__ void __launch_bounds__(256, 3) k_edge_bwd(EdgeBwdArgs p, int ntiles) 
     sb2[j] = swx[j] = sw1[j] = 0.f;
   }
   const TileRange tr = xcd_tile_range(ntiles);
-  for (int tile = tr.first; tile < tr.end; tile += tr.step) {
-    // ---- g_z2 = (alpha*g_M[dst] + c*wx) * silu'(z2): operand-packed to memory, row-major to LDS
-#pragma unroll
-    for (int i = 0; i < C::RB; ++i) {
-      const int rblk = wr * C::RB + i;
-      const int64_t eb = (int64_t)tile * (C::TM / 32) + rblk;
-      if (eb * 32 >= E) continue;
-#pragma unroll
-      for (int vh = 0; vh < 2; ++vh) {
-        int di[8];
-        float cc[8];
-        unsigned ok = 0;
-#pragma unroll
-        for (int jj = 0; jj < 2; ++jj) {
-          const int64_t e4 = eb * 32 + 8 * (2 * vh + jj) + 4 * g;
-          load4(p.dst, e4, E, &di[4 * jj]);
-          load4(p.cvec, e4, E, &cc[4 * jj]);
-#pragma unroll
-          for (int ii = 0; ii < 4; ++ii) ok |= (e4 + ii < E ? 1u : 0u) << (4 * jj + ii);
-        }
-        float gm[C::CB][8];
-        unsigned zw[8];   // PAIRS: z2 of both column blocks, one word per edge
-        if constexpr (PAIRS) {
-          const unsigned* zp = reinterpret_cast<const unsigned*>(p.z2_vm) + (((size_t)eb * (C::NCB / 2) + wc) * 16 + 8 * vh) * 64 + lane;
-#pragma unroll
-          for (int u = 0; u < 8; ++u) zw[u] = __builtin_nontemporal_load(zp + u * 64);
-          const unsigned* __restrict__ U = reinterpret_cast<const unsigned*>(p.gM);
-#pragma unroll
-          for (int u = 0; u < 8; ++u) {
-            const unsigned w = U[di[u] * p.ldgM + wc * 32 + x];
-            gm[0][u] = __uint_as_float(w << 16);
-            gm[1][u] = __uint_as_float(w & 0xffff0000u);
-          }
-        } else {
-          const float* __restrict__ F = reinterpret_cast<const float*>(p.gM);
-#pragma unroll
-          for (int j = 0; j < C::CB; ++j)
-#pragma unroll
-            for (int u = 0; u < 8; ++u) gm[j][u] = F[di[u] * p.ldgM + (wc * C::CB + j) * 32 + x];
-        }
-#pragma unroll
-        for (int j = 0; j < C::CB; ++j) {
-          const int cblk = wc * C::CB + j;
-          const int n = cblk * 32 + x;
-          const size_t zbase = (((size_t)eb * C::NCB + cblk) * 16 + 8 * vh) * 64 + lane;
-          float zz[8], vals[8];
-          if constexpr (PAIRS) {
-#pragma unroll
-            for (int u = 0; u < 8; ++u) zz[u] = j == 0 ? __uint_as_float(zw[u] << 16) : __uint_as_float(zw[u] & 0xffff0000u);
-          } else {
-#pragma unroll
-            for (int u = 0; u < 8; ++u)
-              zz[u] = BF16 ? bf_bits_to_f(__builtin_nontemporal_load(reinterpret_cast<const unsigned short*>(p.z2_vm) + zbase + u * 64))
-                           : __builtin_nontemporal_load(reinterpret_cast<const float*>(p.z2_vm) + zbase + u * 64);
-          }
-#pragma unroll
-          for (int u = 0; u < 8; ++u) {
-            float m, dm;
-            silu_both(zz[u], m, dm);
-            float gz = (p.alpha * gm[j][u] + cc[u] * wxn[j]) * dm;
-            if (!((ok >> u) & 1u)) { gz = 0.f; m = 0.f; }
-            vals[u] = gz;
-            sb2[j] += gz;
-            swx[j] += cc[u] * m;
-          }
-          emit_half<BF16, C::STRIDE>(smem, rblk * 32, g, n, vals, vh, p.gz2_pk, (size_t)eb * C::NCB + cblk, lane);
-        }
-      }
-    }
-    __syncthreads();
-    f32x16_t acc[C::RB][C::CB];
-#pragma unroll
-    for (int i = 0; i < C::RB; ++i)
-#pragma unroll
-      for (int j = 0; j < C::CB; ++j)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-    tile_mma<H, BF16>(smem, p.W2Tp, wr, wc, lane, acc);
-    __syncthreads();
-    // ---- g_z1 = g_a1 * silu'(z1), z1 recomputed from the projected node features
-#pragma unroll
-    for (int i = 0; i < C::RB; ++i) {
-      const int64_t eb = (int64_t)tile * (C::TM / 32) + wr * C::RB + i;
-      if (eb * 32 >= E) continue;
-#pragma unroll
-      for (int vh = 0; vh < 2; ++vh) {
-        int di[8], ci[8];
-        float dd[8];
-#pragma unroll
-        for (int jj = 0; jj < 2; ++jj) {
-          const int64_t e4 = eb * 32 + 8 * (2 * vh + jj) + 4 * g;
-          load4(p.dst, e4, E, &di[4 * jj]);
-          load4(p.col, e4, E, &ci[4 * jj]);
-          load4(p.d2, e4, E, &dd[4 * jj]);
-        }
-        float z[C::CB][8];
-        gather_z1<H, C::CB, PAIRS>(p.PQ, di, ci, dd, w1d, wc, x, z);
-        float gv[C::CB][8];
-#pragma unroll
-        for (int j = 0; j < C::CB; ++j)
-#pragma unroll
-          for (int u = 0; u < 8; ++u) {
-            gv[j][u] = acc[i][j][8 * vh + u] * dsilu_f(z[j][u]);   // rows beyond E have acc == 0
-            sw1[j] += dd[u] * gv[j][u];
-          }
-        if constexpr (PAIRS) {
-          unsigned* o = reinterpret_cast<unsigned*>(p.gz1_vm) + (((size_t)eb * (C::NCB / 2) + wc) * 16 + 8 * vh) * 64 + lane;
-#pragma unroll
-          for (int u = 0; u < 8; ++u) __builtin_nontemporal_store(pack_bf16x2(gv[0][u], gv[1][u]), o + u * 64);
-        } else {
-#pragma unroll
-          for (int j = 0; j < C::CB; ++j) {
-            const size_t base = (((size_t)eb * C::NCB + (wc * C::CB + j)) * 16 + 8 * vh) * 64 + lane;
-            if constexpr (BF16) {
-              unsigned short* o = reinterpret_cast<unsigned short*>(p.gz1_vm) + base;
-#pragma unroll
-              for (int t = 0; t < 4; ++t) {
-                const unsigned pk = pack_bf16x2(gv[j][2 * t], gv[j][2 * t + 1]);
-                __builtin_nontemporal_store((unsigned short)(pk & 0xffffu), o + (2 * t) * 64);
-                __builtin_nontemporal_store((unsigned short)(pk >> 16), o + (2 * t + 1) * 64);
-              }
-            } else {
-              float* o = reinterpret_cast<float*>(p.gz1_vm) + base;
-#pragma unroll
-              for (int u = 0; u < 8; ++u) __builtin_nontemporal_store(gv[j][u], o + u * 64);
-            }
-          }
-        }
-      }
-    }
+  sc[tid] = fetch_edge_scalar<C::TM, 4>(p.dst, p.col, p.d2, p.cvec, tr.first, tr.end, E, tid);
+  __syncthreads();
+  int buf = 0;
+  for (int tile = tr.first; tile < tr.end; tile += tr.step, buf ^= 1) {
+    // the next tile's scalars travel while this tile is processed
+    const int nxt = fetch_edge_scalar<C::TM, 4>(p.dst, p.col, p.d2, p.cvec, tile + tr.step, tr.end, E, tid);
+    const int* s = sc + buf * 4 * C::TM;
+    int* s_next = sc + (buf ^ 1) * 4 * C::TM;
+    if ((tile + 1) * C::TM <= E)
+      edge_bwd_tile<H, BF16, true>(p, smem, s, s_next, nxt, tile, E, tid, wr, wc, lane, w1d, wxn, sb2, swx, sw1);
+    else
+      edge_bwd_tile<H, BF16, false>(p, smem, s, s_next, nxt, tile, E, tid, wr, wc, lane, w1d, wxn, sb2, swx, sw1);
   }
   // ---- per-column partial sums of this wavefront: combine the two lane halves, one writer per column
 #pragma unroll
@@ -777,7 +866,7 @@ static int32_t launch_edge_bwd_t(hipStream_t st, const EdgeBwdArgs& a) {
   static bool attr_set = false;
   if (!attr_set) {
     HGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_edge_bwd<H, BF16>),
-                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES));
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)(C::LDS_BYTES + 8 * C::TM * 4)));
     attr_set = true;
   }
   int64_t grid = (int64_t)num_cus() * 3;   // three workgroups are resident per CU
@@ -786,7 +875,7 @@ static int32_t launch_edge_bwd_t(hipStream_t st, const EdgeBwdArgs& a) {
   if (grid < 1) grid = 1;  // E == 0: one block writes zero partials
   {
     ProfScope ps(PT_EDGE_FUSED_BWD, st);
-    k_edge_bwd<H, BF16><<<dim3((unsigned)grid), 256, C::LDS_BYTES, st>>>(a, (int)ntiles);
+    k_edge_bwd<H, BF16><<<dim3((unsigned)grid), 256, C::LDS_BYTES + 8 * C::TM * 4, st>>>(a, (int)ntiles);
     HGNN_LAUNCH_CHECK("k_edge_bwd");
   }
   float* dest[4] = {a.g_b2, a.g_wx, a.g_w1d, nullptr};
@@ -794,6 +883,10 @@ static int32_t launch_edge_bwd_t(hipStream_t st, const EdgeBwdArgs& a) {
 }
 
 int32_t launch_edge_bwd(hipStream_t st, int H, bool bf16, const EdgeBwdArgs& a) {
+  HGNN_REQUIRE(a.E >= 0 && a.E <= EDGE_MAX_E, HGNN_ERR_BAD_SHAPE, "edge kernels index edges with 32 bits (E = %lld)",
+               (long long)a.E);
+  HGNN_REQUIRE(a.ldgM == (edge_pairs(H, bf16) ? H / 2 : 2 * H), HGNN_ERR_BAD_SHAPE,
+               "g_M must be the second half of a [N,2H] tensor, or [N,H/2] words of bf16 pairs");
   switch (H) {
     case 64: return bf16 ? launch_edge_bwd_t<64, true>(st, a) : launch_edge_bwd_t<64, false>(st, a);
     case 128: return bf16 ? launch_edge_bwd_t<128, true>(st, a) : launch_edge_bwd_t<128, false>(st, a);

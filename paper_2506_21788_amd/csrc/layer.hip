@@ -113,7 +113,10 @@ static int32_t stream_after(hipStream_t to, hipStream_t from, hipEvent_t ev) {
 
 static int32_t check_layer_args(int N, int64_t E, int H, int dtype) {
   HGNN_REQUIRE(N >= 0 && E >= 0, HGNN_ERR_BAD_SHAPE, "negative N or E");
-  HGNN_REQUIRE(E < (1ll << 31) / 1, HGNN_ERR_OVERFLOW, "edge count does not fit int32");
+  HGNN_REQUIRE(E <= 2147483647LL - 128, HGNN_ERR_OVERFLOW, "edge count does not fit the 32-bit edge indices");
+  // the edge kernels gather rows of [N,2H] fp32 node tensors at 32-bit byte offsets
+  HGNN_REQUIRE((int64_t)N * 2 * H * 4 < (1ll << 32), HGNN_ERR_OVERFLOW,
+               "N * 2H * 4 bytes must stay below 4 GiB (N = %d, H = %d)", N, H);
   HGNN_REQUIRE(valid_H(H), HGNN_ERR_BAD_SHAPE, "H must be 64, 128 or 256 (got %d)", H);
   HGNN_REQUIRE(dtype == HGNN_F32 || dtype == HGNN_BF16, HGNN_ERR_BAD_SHAPE, "unknown dtype %d", dtype);
   return HGNN_OK;
