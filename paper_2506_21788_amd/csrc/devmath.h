@@ -24,7 +24,7 @@ __device__ __forceinline__ void silu_both(float t, float& y, float& dy) {
   const float e = __expf(-t);
   const float s = __builtin_amdgcn_rcpf(1.0f + e);
   y = t * s;
-  dy = s * (1.0f + t * (1.0f - s));
+  dy = fmaf(y, 1.0f - s, s);   // s (1 + t (1 - s))
 }
 
 // float -> bf16, round to nearest even, through the packed hardware conversion (v_cvt_pk_bf16_f32)

@@ -53,7 +53,7 @@ struct EdgeBwdArgs {
   const float* w1d;
   const void* W2Tp;    // packed W2^T block
   const void* z2_vm;   // saved by the forward kernel
-  const void* gM;      // gradient of the aggregated messages: fp32 [N, ldgM], or bf16 pairs [N, ldgM words]
+  const void* gM;      // gradient of the aggregated messages: fp32 [N, ldgM], or alpha * g_M as bf16 pairs [N, ldgM words]
   int ldgM;
   const float* cvec;   // [E] c_e = alpha * (g_v[dst[e]] . rvec[e])
   const float* wx;     // [H]

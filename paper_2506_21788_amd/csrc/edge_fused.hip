@@ -10,6 +10,8 @@
 // All element-wise work uses the accumulator mapping (lane <-> column, register <-> edge), so what one
 // kernel stores is what the next one loads, coalesced, without any transpose. Every sum has a fixed
 // order; there are no atomics.
+#include <type_traits>
+
 #include "devmath.h"
 #include "edge_fused.h"
 #include "gemm.h"
@@ -118,15 +120,16 @@ __device__ __forceinline__ TileRange xcd_tile_range(int ntiles) {
   return {lo + slot, hi, G >> 3};
 }
 
-// A tile (LDS, row-major, padded) x packed B block -> accumulators; same tiling as the row-tile GEMM
+// A tile (LDS, row-major, padded) x packed B block -> accumulators; same tiling as the row-tile GEMM.
+// The accumulators start from zero (the first step feeds a constant zero, so they need no clearing).
 template <int H, bool BF16>
 __device__ __forceinline__ void tile_mma(const unsigned char* smem, const void* Bpacked, int wr, int wc, int lane,
                                          f32x16_t (&acc)[ECfg<H, BF16>::RB][ECfg<H, BF16>::CB]) {
   using C = ECfg<H, BF16>;
-  if (BF16) {
+  const f32x16_t zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  if constexpr (BF16) {
     constexpr int NKB = H / 16;
-#pragma unroll 4
-    for (int kb = 0; kb < NKB; ++kb) {
+    auto step = [&](int kb, auto first) {
       bf16x8_t a[C::RB];
 #pragma unroll
       for (int i = 0; i < C::RB; ++i) {
@@ -137,13 +140,20 @@ __device__ __forceinline__ void tile_mma(const unsigned char* smem, const void* 
       for (int j = 0; j < C::CB; ++j) {
         const bf16x8_t b = ldg_at<bf16x8_t>(uoff(Bpacked, (size_t)((wc * C::CB + j) * NKB + kb) * 1024), lane * 16u);
 #pragma unroll
-        for (int i = 0; i < C::RB; ++i) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b, acc[i][j], 0, 0, 0);
+        for (int i = 0; i < C::RB; ++i)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b, decltype(first)::value ? zero : acc[i][j], 0, 0, 0);
       }
-    }
+    };
+    static_assert(NKB % 4 == 0, "steps are taken four at a time");
+    step(0, std::true_type{});
+    step(1, std::false_type{});
+    step(2, std::false_type{});
+    step(3, std::false_type{});
+#pragma unroll 4
+    for (int kb = 4; kb < NKB; ++kb) step(kb, std::false_type{});
   } else {
     constexpr int NKB = H / 8;
-#pragma unroll 4
-    for (int kb = 0; kb < NKB; ++kb) {
+    auto step = [&](int kb, auto first) {
       float4 a[C::RB];
 #pragma unroll
       for (int i = 0; i < C::RB; ++i) {
@@ -155,13 +165,20 @@ __device__ __forceinline__ void tile_mma(const unsigned char* smem, const void* 
         const float4 b = ldg_at<float4>(uoff(Bpacked, (size_t)((wc * C::CB + j) * NKB + kb) * 1024), lane * 16u);
 #pragma unroll
         for (int i = 0; i < C::RB; ++i) {
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].x, b.x, acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].x, b.x, decltype(first)::value ? zero : acc[i][j], 0, 0, 0);
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].y, b.y, acc[i][j], 0, 0, 0);
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].z, b.z, acc[i][j], 0, 0, 0);
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].w, b.w, acc[i][j], 0, 0, 0);
         }
       }
-    }
+    };
+    static_assert(NKB % 4 == 0, "steps are taken four at a time");
+    step(0, std::true_type{});
+    step(1, std::false_type{});
+    step(2, std::false_type{});
+    step(3, std::false_type{});
+#pragma unroll 4
+    for (int kb = 4; kb < NKB; ++kb) step(kb, std::false_type{});
   }
 }
 
@@ -730,7 +747,7 @@ __device__ __forceinline__ void edge_bwd_tile(const EdgeBwdArgs& p, unsigned cha
         for (int u = 0; u < 8; ++u) {
           float m, dm;
           silu_both(zz[u], m, dm);
-          float gz = (p.alpha * gm[j][u] + cc[u] * wxn[j]) * dm;
+          float gz = fmaf(cc[u], wxn[j], PAIRS ? gm[j][u] : p.alpha * gm[j][u]) * dm;   // the pair form holds alpha * g_M
           if (!FULL && !((ok >> u) & 1u)) gz = 0.f;   // c is zero there, so the wx sum needs no mask
           vals[u] = gz;
           sb2[j] += gz;
@@ -746,12 +763,6 @@ __device__ __forceinline__ void edge_bwd_tile(const EdgeBwdArgs& p, unsigned cha
   }
   __syncthreads();
   f32x16_t acc[C::RB][C::CB];
-#pragma unroll
-  for (int i = 0; i < C::RB; ++i)
-#pragma unroll
-    for (int j = 0; j < C::CB; ++j)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
   tile_mma<H, BF16>(smem, p.W2Tp, wr, wc, lane, acc);
   s_next[tid] = nxt;
   __syncthreads();

@@ -59,6 +59,7 @@ struct GemmArgs {
   int ldpair = 0;
   int pair_cb_mask = 0;
   int pair_off[2] = {0, 0};
+  float pair_scale = 1.f;   // factor on the pair output (after the bias)
   int tag = PT_GEMM_NODE;  // timing class
 };
 int32_t launch_gemm(hipStream_t st, int H, bool bf16, const GemmArgs& a);

@@ -235,7 +235,7 @@ __global__ void __launch_bounds__(256, 2) k_gemm(GemmArgs p) {
           if (pos < rend) {
             const long gr = p.row_idx ? p.row_idx[pos] : pos;
             p.Cpair[gr * p.ldpair + p.pair_off[cb] + wc * 32 + (lane & 31)] =
-                pack_bf16x2(acc[i][0][v] + b0, acc[i][1][v] + b1);
+                pack_bf16x2((acc[i][0][v] + b0) * p.pair_scale, (acc[i][1][v] + b1) * p.pair_scale);
           }
         }
       }

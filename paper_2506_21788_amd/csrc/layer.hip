@@ -299,6 +299,7 @@ extern "C" int32_t hgnn_mp_layer_bwd(void* stream, int32_t N, int64_t E, int32_t
     g.C = w.g_hM; g.ldc = 2 * H;
     if (edge_pairs(H, bf16)) {   // the g_M half goes out as bf16 pairs for the fused edge kernel
       g.Cpair = w.gM_pk; g.ldpair = H / 2; g.pair_cb_mask = 2; g.pair_off[1] = 0;
+      g.pair_scale = alpha;   // the pair form carries alpha * g_M
     }
     HGNN_TRY(launch_gemm(st, H, bf16, g));
   }
