@@ -911,7 +911,7 @@ int32_t launch_edge_bwd(hipStream_t st, int H, bool bf16, const EdgeBwdArgs& a) 
 // ---------------------------------------------------------------------------------------------
 template <int H, bool BF16>
 __global__ void __launch_bounds__(256)
-k_wgrad_frag(int64_t nblk32, int blocks_per_wg, const void* __restrict__ a1_pk, const void* __restrict__ gz2_pk,
+k_wgrad_frag(int64_t nblk32, const void* __restrict__ a1_pk, const void* __restrict__ gz2_pk,
              float* __restrict__ partial) {
   constexpr int NCB = H / 32;
   constexpr int NBW = NCB / 2;  // 32-blocks per wavefront along each output dimension
@@ -924,66 +924,83 @@ k_wgrad_frag(int64_t nblk32, int blocks_per_wg, const void* __restrict__ a1_pk, 
     for (int j = 0; j < NBW; ++j)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-  int64_t eb0 = (int64_t)blockIdx.x * blocks_per_wg;
-  int64_t eb1 = eb0 + blocks_per_wg;
-  if (eb1 > nblk32) eb1 = nblk32;
+  // 32-edge blocks are dealt round-robin: at any moment the workgroups together read one contiguous window of
+  // each operand (DRAM page locality), and every workgroup still sums its blocks in a fixed order
+  const int64_t G = gridDim.x;
+  const int64_t nmine = nblk32 > (int64_t)blockIdx.x ? (nblk32 - blockIdx.x + G - 1) / G : 0;
   // one chunk = one matrix-core operand per block column: 16 edges (bf16) or 4 edges (fp32, four instructions);
-  // chunks are double buffered in registers so that the loads of the next one overlap the products of this one
+  // four chunk buffers in registers keep three chunks of loads in flight behind the products of the current one
   constexpr int CPB = BF16 ? 2 : 4;   // chunks per 32-edge block
-  const int64_t nchunk = (eb1 > eb0) ? (eb1 - eb0) * CPB : 0;
+  const int64_t nchunk = nmine * CPB;
 #define HGNN_WG_LOAD(c, a, b)                                                                          \
   {                                                                                                    \
-    const size_t eb_ = (size_t)(eb0 + (c) / CPB);                                                      \
+    const size_t eb_ = (size_t)(blockIdx.x + ((c) / CPB) * G);                                         \
     const int sub_ = (int)((c) % CPB);                                                                 \
     _Pragma("unroll") for (int i = 0; i < NBW; ++i) {                                                  \
       a[i] = __builtin_nontemporal_load(A + ((eb_ * NCB + wa * NBW + i) * CPB + sub_) * 64 + lane);    \
       b[i] = __builtin_nontemporal_load(B + ((eb_ * NCB + wb * NBW + i) * CPB + sub_) * 64 + lane);    \
     }                                                                                                  \
   }
+  // The loop takes four chunks per trip without any branch around the products (a branch there makes the compiler
+  // copy the accumulators). Loads past the end are clamped to the last chunk and their A operand is replaced by
+  // zeros when it is used, so the extra products of the last trip add nothing.
+#define HGNN_WG_CL(c) ((c) < nchunk ? (c) : nchunk - 1)
+#define HGNN_WG_PIPELINE                                                                               \
+  if (nchunk > 0) {                                                                                    \
+    HGNN_WG_LOAD(0, a0, b0)                                                                            \
+    HGNN_WG_LOAD(HGNN_WG_CL(1), a1, b1)                                                                \
+    HGNN_WG_LOAD(HGNN_WG_CL(2), a2, b2)                                                                \
+    for (int64_t c = 0; c < nchunk; c += 4) {                                                          \
+      HGNN_WG_LOAD(HGNN_WG_CL(c + 3), a3, b3)                                                          \
+      HGNN_WG_MMA(a0, b0, true)                                                                        \
+      HGNN_WG_LOAD(HGNN_WG_CL(c + 4), a0, b0)                                                          \
+      HGNN_WG_MMA(a1, b1, c + 1 < nchunk)                                                              \
+      HGNN_WG_LOAD(HGNN_WG_CL(c + 5), a1, b1)                                                          \
+      HGNN_WG_MMA(a2, b2, c + 2 < nchunk)                                                              \
+      HGNN_WG_LOAD(HGNN_WG_CL(c + 6), a2, b2)                                                          \
+      HGNN_WG_MMA(a3, b3, c + 3 < nchunk)                                                              \
+    }                                                                                                  \
+  }
   if constexpr (BF16) {
     const bf16x8_t* __restrict__ A = reinterpret_cast<const bf16x8_t*>(a1_pk);
     const bf16x8_t* __restrict__ B = reinterpret_cast<const bf16x8_t*>(gz2_pk);
-    bf16x8_t a0[NBW], b0[NBW], a1[NBW], b1[NBW];
-#define HGNN_WG_MMA(a, b)                                                                              \
-  _Pragma("unroll") for (int i = 0; i < NBW; ++i) _Pragma("unroll") for (int j = 0; j < NBW; ++j)      \
-      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
-    // nchunk is even; the prefetch past the end is clamped to the last chunk (loaded again, never used)
-    if (nchunk > 0) {
-      HGNN_WG_LOAD(0, a0, b0)
-      for (int64_t c = 0; c < nchunk; c += 2) {
-        HGNN_WG_LOAD(c + 1, a1, b1)
-        HGNN_WG_MMA(a0, b0)
-        const int64_t cn = c + 2 < nchunk ? c + 2 : nchunk - 1;
-        HGNN_WG_LOAD(cn, a0, b0)
-        HGNN_WG_MMA(a1, b1)
-      }
-    }
+    bf16x8_t a0[NBW], b0[NBW], a1[NBW], b1[NBW], a2[NBW], b2[NBW], a3[NBW], b3[NBW];
+#define HGNN_WG_MMA(a, b, valid)                                                                       \
+  {                                                                                                    \
+    const bool ok_ = (valid);                                                                          \
+    const bf16x8_t zero_ = {0, 0, 0, 0, 0, 0, 0, 0};                                                   \
+    _Pragma("unroll") for (int i = 0; i < NBW; ++i) {                                                  \
+      const bf16x8_t az_ = ok_ ? a[i] : zero_;                                                         \
+      _Pragma("unroll") for (int j = 0; j < NBW; ++j)                                                  \
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(az_, b[j], acc[i][j], 0, 0, 0);          \
+    }                                                                                                  \
+  }
+    HGNN_WG_PIPELINE
 #undef HGNN_WG_MMA
   } else {
     const f32x4_t* __restrict__ A = reinterpret_cast<const f32x4_t*>(a1_pk);
     const f32x4_t* __restrict__ B = reinterpret_cast<const f32x4_t*>(gz2_pk);
-    f32x4_t a0[NBW], b0[NBW], a1[NBW], b1[NBW];
-#define HGNN_WG_MMA(a, b)                                                                              \
-  _Pragma("unroll") for (int i = 0; i < NBW; ++i) _Pragma("unroll") for (int j = 0; j < NBW; ++j) {    \
-    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i][0], b[j][0], acc[i][j], 0, 0, 0);            \
-    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i][1], b[j][1], acc[i][j], 0, 0, 0);            \
-    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i][2], b[j][2], acc[i][j], 0, 0, 0);            \
-    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i][3], b[j][3], acc[i][j], 0, 0, 0);            \
+    f32x4_t a0[NBW], b0[NBW], a1[NBW], b1[NBW], a2[NBW], b2[NBW], a3[NBW], b3[NBW];
+#define HGNN_WG_MMA(a, b, valid)                                                                       \
+  {                                                                                                    \
+    const bool ok_ = (valid);                                                                          \
+    const f32x4_t zero_ = {0.f, 0.f, 0.f, 0.f};                                                        \
+    _Pragma("unroll") for (int i = 0; i < NBW; ++i) {                                                  \
+      const f32x4_t az_ = ok_ ? a[i] : zero_;                                                          \
+      _Pragma("unroll") for (int j = 0; j < NBW; ++j) {                                                \
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(az_[0], b[j][0], acc[i][j], 0, 0, 0);         \
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(az_[1], b[j][1], acc[i][j], 0, 0, 0);         \
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(az_[2], b[j][2], acc[i][j], 0, 0, 0);         \
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(az_[3], b[j][3], acc[i][j], 0, 0, 0);         \
+      }                                                                                                \
+    }                                                                                                  \
   }
-    // nchunk is even; the prefetch past the end is clamped to the last chunk (loaded again, never used)
-    if (nchunk > 0) {
-      HGNN_WG_LOAD(0, a0, b0)
-      for (int64_t c = 0; c < nchunk; c += 2) {
-        HGNN_WG_LOAD(c + 1, a1, b1)
-        HGNN_WG_MMA(a0, b0)
-        const int64_t cn = c + 2 < nchunk ? c + 2 : nchunk - 1;
-        HGNN_WG_LOAD(cn, a0, b0)
-        HGNN_WG_MMA(a1, b1)
-      }
-    }
+    HGNN_WG_PIPELINE
 #undef HGNN_WG_MMA
   }
 #undef HGNN_WG_LOAD
+#undef HGNN_WG_PIPELINE
+#undef HGNN_WG_CL
   float* out = partial + (size_t)blockIdx.x * H * H;
 #pragma unroll
   for (int i = 0; i < NBW; ++i)
@@ -1008,10 +1025,9 @@ static int32_t launch_wgrad_frag_t(hipStream_t st, int64_t E, const void* a1_pk,
   if (grid > WGRAD_FRAG_MAX_GRID) grid = WGRAD_FRAG_MAX_GRID;
   if (grid > nblk32) grid = nblk32;
   if (grid < 1) grid = 1;
-  const int64_t per = nblk32 > 0 ? (nblk32 + grid - 1) / grid : 0;
   {
     ProfScope ps(PT_WGRAD_EDGE, st);
-    k_wgrad_frag<H, BF16><<<dim3((unsigned)grid), 256, 0, st>>>(nblk32, (int)per, a1_pk, gz2_pk, partial);
+    k_wgrad_frag<H, BF16><<<dim3((unsigned)grid), 256, 0, st>>>(nblk32, a1_pk, gz2_pk, partial);
     HGNN_LAUNCH_CHECK("k_wgrad_frag");
   }
   float* dest[4] = {gW2, nullptr, nullptr, nullptr};
