@@ -84,7 +84,10 @@ struct GemmCfg {
   static constexpr int RB = WROWS / 32;
   static constexpr int CB = WCOLS / 32;
   static constexpr int STRIDE = BF16 ? H + 8 : H + 4;    // LDS row pitch in elements (bank spread)
-  static constexpr size_t LDS_BYTES = (size_t)TM * STRIDE * (BF16 ? 2 : 4);
+  static constexpr int CSTR = H + 4;                      // epilogue staging row pitch (floats)
+  static constexpr size_t A_BYTES = (size_t)TM * STRIDE * (BF16 ? 2 : 4);
+  static constexpr size_t C_BYTES = (size_t)WR * 32 * CSTR * 4;
+  static constexpr size_t LDS_BYTES = A_BYTES > C_BYTES ? A_BYTES : C_BYTES;
   static_assert(WROWS % 32 == 0 && (TM * (H / 4)) % 256 == 0, "tile height does not fit the wavefront grid");
 };
 
@@ -169,14 +172,17 @@ __global__ void __launch_bounds__(256, 2) k_gemm(GemmArgs p) {
       }
     }
     __syncthreads();
-    // ---- multiply
+    // ---- multiply. All workgroups run this loop at about the same time over the same packed block: each starts at
+    // a different k step so that they do not all ask the same L2 lines at once.
+    const int krot = blockIdx.x * 5;
     const long bblk0 = grp * p.grp_blk_stride + p.blk[kc][cb];
     if (BF16) {
       const bf16x8_t* __restrict__ Bp = reinterpret_cast<const bf16x8_t*>(p.B) + bblk0 * (H * H / 8);
       constexpr int NKB = H / 16;
       constexpr int KUN = C::TM > 64 ? 4 : 8;   // operand loads in flight; fewer with the taller tile's accumulators
 #pragma unroll KUN
-      for (int kb = 0; kb < NKB; ++kb) {
+      for (int kk = 0; kk < NKB; ++kk) {
+        const int kb = (kk + krot) & (NKB - 1);
         bf16x8_t a[C::RB];
 #pragma unroll
         for (int i = 0; i < C::RB; ++i) {
@@ -196,7 +202,8 @@ __global__ void __launch_bounds__(256, 2) k_gemm(GemmArgs p) {
       const float4* __restrict__ Bp = reinterpret_cast<const float4*>(p.B) + bblk0 * (H * H / 4);
       constexpr int NKB = H / 8;
 #pragma unroll 4
-      for (int kb = 0; kb < NKB; ++kb) {
+      for (int kk = 0; kk < NKB; ++kk) {
+        const int kb = (kk + krot) & (NKB - 1);
         float4 a[C::RB];
 #pragma unroll
         for (int i = 0; i < C::RB; ++i) {
@@ -219,61 +226,91 @@ __global__ void __launch_bounds__(256, 2) k_gemm(GemmArgs p) {
     }
   }
 
-  // ---- epilogue on the accumulator registers
+  // ---- epilogue: the accumulators go through LDS, one 32-row block per wavefront row at a time, so that the
+  // auxiliary operands and C are accessed row-major with 16-byte loads and stores (few, wide, whole cache lines)
   const bool use_bias = p.bias && ((p.bias_cb_mask >> cb) & 1);
-  if constexpr (C::CB == 2) {
-    if ((p.pair_cb_mask >> cb) & 1) {   // bf16 pairs: this lane's two column blocks share one 32-bit word
-      const int c0 = wc * C::WCOLS + (lane & 31);
-      const float b0 = use_bias ? p.bias[grp * p.grp_bias_stride + c0] : 0.f;
-      const float b1 = use_bias ? p.bias[grp * p.grp_bias_stride + c0 + 32] : 0.f;
+  const bool pair_out = C::CB == 2 && ((p.pair_cb_mask >> cb) & 1);
+  constexpr int CH = H / 4;                 // 4-column chunks per row
+  constexpr int PROWS = C::WR * 32;         // rows per pass
+  constexpr int RSTEP = 256 / CH;           // rows swept by the 256 threads at once
+  constexpr int NCH = PROWS / RSTEP;        // chunks per thread and pass
+  float* cst = reinterpret_cast<float*>(smem);
+  const int q = tid % CH, r0 = tid / CH;
+  float4 bv = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (use_bias && !pair_out) bv = *reinterpret_cast<const float4*>(p.bias + grp * p.grp_bias_stride + q * 4);
 #pragma unroll
-      for (int i = 0; i < C::RB; ++i) {
+  for (int i = 0; i < C::RB; ++i) {
+    __syncthreads();   // nobody reads the A tile (or the previous pass) any more
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int r = wr * C::WROWS + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-          const int pos = rbeg + r;
+    for (int j = 0; j < C::CB; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v)
+        cst[(wr * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3)) * C::CSTR + wc * C::WCOLS + j * 32 + (lane & 31)] = acc[i][j][v];
+    __syncthreads();
+    if (pair_out) {
+      if constexpr (C::CB == 2) {
+        // bf16 pairs: word w = wc'*32 + x' of a row holds columns wc'*64 + x' and wc'*64 + 32 + x'
+        constexpr int WCH = H / 8;          // 4-word chunks per row
+        constexpr int WSTEP = 256 / WCH;
+        const int qw = tid % WCH, rw0 = tid / WCH;
+        const int c_lo = (qw * 4 / 32) * 64 + (qw * 4) % 32;
+        float4 b_lo = make_float4(0.f, 0.f, 0.f, 0.f), b_hi = b_lo;
+        if (use_bias) {
+          b_lo = *reinterpret_cast<const float4*>(p.bias + grp * p.grp_bias_stride + c_lo);
+          b_hi = *reinterpret_cast<const float4*>(p.bias + grp * p.grp_bias_stride + c_lo + 32);
+        }
+#pragma unroll
+        for (int k = 0; k < PROWS / WSTEP; ++k) {
+          const int sr = rw0 + k * WSTEP;
+          const int pos = rbeg + (sr / 32) * C::WROWS + i * 32 + (sr % 32);
           if (pos < rend) {
             const long gr = p.row_idx ? p.row_idx[pos] : pos;
-            p.Cpair[gr * p.ldpair + p.pair_off[cb] + wc * 32 + (lane & 31)] =
-                pack_bf16x2((acc[i][0][v] + b0) * p.pair_scale, (acc[i][1][v] + b1) * p.pair_scale);
+            const float4 lo = *reinterpret_cast<const float4*>(cst + sr * C::CSTR + c_lo);
+            const float4 hi = *reinterpret_cast<const float4*>(cst + sr * C::CSTR + c_lo + 32);
+            uint4 o;
+            o.x = pack_bf16x2((lo.x + b_lo.x) * p.pair_scale, (hi.x + b_hi.x) * p.pair_scale);
+            o.y = pack_bf16x2((lo.y + b_lo.y) * p.pair_scale, (hi.y + b_hi.y) * p.pair_scale);
+            o.z = pack_bf16x2((lo.z + b_lo.z) * p.pair_scale, (hi.z + b_hi.z) * p.pair_scale);
+            o.w = pack_bf16x2((lo.w + b_lo.w) * p.pair_scale, (hi.w + b_hi.w) * p.pair_scale);
+            *reinterpret_cast<uint4*>(p.Cpair + gr * p.ldpair + p.pair_off[cb] + qw * 4) = o;
           }
         }
       }
-      return;
-    }
-  }
+    } else {
+      const int gcol = cb * H + q * 4;
+      long grow[NCH];
+      bool ok[NCH];
+      float4 mv[NCH], a1[NCH], a2[NCH];
+      // every auxiliary load of the pass is issued before any result is stored (rows past the end are clamped)
 #pragma unroll
-  for (int i = 0; i < C::RB; ++i) {
-    // the 16 rows of this lane in row block i (clamped to the last valid row so that every load below is
-    // unconditional and all of them can be in flight together)
-    int grow[16];
-#pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const int r = wr * C::WROWS + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-      int pos = rbeg + r;
-      pos = pos < rend ? pos : rend - 1;
-      grow[v] = p.row_idx ? p.row_idx[pos] : pos;
-    }
-#pragma unroll
-    for (int j = 0; j < C::CB; ++j) {
-      const int col = wc * C::WCOLS + j * 32 + (lane & 31);
-      const int gcol = cb * H + col;
-      const float bv = use_bias ? p.bias[grp * p.grp_bias_stride + col] : 0.f;
-      float mv[16], a1[16], a2[16];
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        mv[v] = p.mul ? p.mul[(long)grow[v] * p.ldmul + gcol] : 1.f;
-        a1[v] = p.add1 ? p.add1[(long)grow[v] * p.ldadd1 + gcol] : 0.f;
-        a2[v] = p.add2 ? p.add2[(long)grow[v] * p.ldadd2 + gcol] : 0.f;
+      for (int k = 0; k < NCH; ++k) {
+        const int sr = r0 + k * RSTEP;
+        int pos = rbeg + (sr / 32) * C::WROWS + i * 32 + (sr % 32);
+        ok[k] = pos < rend;
+        pos = ok[k] ? pos : rend - 1;
+        grow[k] = p.row_idx ? p.row_idx[pos] : pos;
       }
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int r = wr * C::WROWS + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-        if (rbeg + r < rend) {
-          float x = acc[i][j][v] + bv;
-          if (p.mul) x *= p.mul_is_z ? dsilu_f(mv[v]) : mv[v];
-          p.C[(long)grow[v] * p.ldc + gcol] = x + a1[v] + a2[v];
+      for (int k = 0; k < NCH; ++k) {
+        if (p.mul) mv[k] = *reinterpret_cast<const float4*>(p.mul + grow[k] * p.ldmul + gcol);
+        if (p.add1) a1[k] = *reinterpret_cast<const float4*>(p.add1 + grow[k] * p.ldadd1 + gcol);
+        if (p.add2) a2[k] = *reinterpret_cast<const float4*>(p.add2 + grow[k] * p.ldadd2 + gcol);
+      }
+#pragma unroll
+      for (int k = 0; k < NCH; ++k) {
+        const int sr = r0 + k * RSTEP;
+        float4 x = *reinterpret_cast<const float4*>(cst + sr * C::CSTR + q * 4);
+        x.x += bv.x; x.y += bv.y; x.z += bv.z; x.w += bv.w;
+        if (p.mul) {
+          if (p.mul_is_z) {
+            x.x *= dsilu_f(mv[k].x); x.y *= dsilu_f(mv[k].y); x.z *= dsilu_f(mv[k].z); x.w *= dsilu_f(mv[k].w);
+          } else {
+            x.x *= mv[k].x; x.y *= mv[k].y; x.z *= mv[k].z; x.w *= mv[k].w;
+          }
         }
+        if (p.add1) { x.x += a1[k].x; x.y += a1[k].y; x.z += a1[k].z; x.w += a1[k].w; }
+        if (p.add2) { x.x += a2[k].x; x.y += a2[k].y; x.z += a2[k].z; x.w += a2[k].w; }
+        if (ok[k]) *reinterpret_cast<float4*>(p.C + grow[k] * p.ldc + gcol) = x;
       }
     }
   }
