@@ -499,10 +499,10 @@ __global__ void __launch_bounds__(256) k_wgrad(WgradArgs p, int nsplit, int rows
   const float* __restrict__ B = p.B[ib];
   const int lda = p.lda[ia], ldb = p.ldb[ib];
   constexpr int CH = C::OT / 4;
-  for (long r0 = rbeg; r0 < rend; r0 += WG_RC) {
-    __syncthreads();
-    constexpr int ITER = WG_RC * CH / 256;   // 1, 2 or 4
-    float4 va[ITER], vb[ITER];
+  constexpr int ITER = WG_RC * CH / 256;   // 1, 2 or 4
+  float4 va[ITER], vb[ITER];
+  // the rows of step r0 (clamped to the last valid row; rows past the end are zeroed when they are staged)
+  auto fetch = [&](long r0) {
 #pragma unroll
     for (int u = 0; u < ITER; ++u) {
       const int c = tid + u * 256;
@@ -513,6 +513,10 @@ __global__ void __launch_bounds__(256) k_wgrad(WgradArgs p, int nsplit, int rows
       va[u] = *reinterpret_cast<const float4*>(A + gr * lda + ta * C::OT + q * 4);
       vb[u] = *reinterpret_cast<const float4*>(B + gr * ldb + tb * C::OT + q * 4);
     }
+  };
+  if (rbeg < rend) fetch(rbeg);
+  for (long r0 = rbeg; r0 < rend; r0 += WG_RC) {
+    __syncthreads();
 #pragma unroll
     for (int u = 0; u < ITER; ++u) {
       const int c = tid + u * 256;
@@ -523,6 +527,8 @@ __global__ void __launch_bounds__(256) k_wgrad(WgradArgs p, int nsplit, int rows
       *reinterpret_cast<float4*>(&sA[r * C::STRIDE + q * 4]) = a;
       *reinterpret_cast<float4*>(&sB[r * C::STRIDE + q * 4]) = b;
     }
+    // the next step's rows travel while this step is multiplied
+    if (r0 + WG_RC < rend) fetch(r0 + WG_RC);
     __syncthreads();
     if (BF16) {
 #pragma unroll
@@ -596,12 +602,16 @@ size_t wgrad_partial_floats(int H, int64_t M, int nblocks, int S) {
 template <int H, bool BF16>
 static int32_t launch_wgrad_t(hipStream_t st, const WgradArgs& a) {
   using C = WgradCfg<H>;
-  const int nsplit = wgrad_splits(a.M);
+  const int nblk = a.nA * a.nB;
+  const int groups = a.grp_ptr ? a.S : 1;
+  // as many splits as keep the launch within one round of resident workgroups (three per CU), never more than
+  // the workspace was sized for
+  int nsplit = wgrad_splits(a.M);
+  const long fit = 3L * num_cus() / ((long)nblk * C::TILES * C::TILES * groups);
+  if (nsplit > fit) nsplit = fit < 1 ? 1 : (int)fit;
   int64_t rps = (a.M + nsplit - 1) / nsplit;
   rps = (rps + WG_RC - 1) / WG_RC * WG_RC;
   if (rps < WG_RC) rps = WG_RC;
-  const int nblk = a.nA * a.nB;
-  const int groups = a.grp_ptr ? a.S : 1;
   ProfScope ps(a.tag, st);
   k_wgrad<H, BF16><<<dim3(nsplit, nblk * C::TILES * C::TILES, groups), 256, 0, st>>>(a, nsplit, (int)rps);
   HGNN_LAUNCH_CHECK("k_wgrad");
