@@ -35,7 +35,7 @@ struct EdgeFwdArgs {
   const float* w1d;    // [H]
   const void* W2p;     // packed W2 block
   const float* b2;     // [H]
-  void* a1_pk;         // out: silu(z1), operand-packed (bf16 or fp32)
+  void* a1_pk;         // out: silu(z1), operand-packed (bf16 or fp32); null: not stored
   void* z2_vm;         // out: z2, v-major (bf16 or fp32)
 };
 int32_t launch_edge_fwd(hipStream_t st, int H, bool bf16, const EdgeFwdArgs& a);
@@ -76,6 +76,12 @@ int32_t launch_edge_cvec(hipStream_t st, int64_t E, const int32_t* dst, const fl
 size_t wgrad_frag_partial_floats(int H);
 int32_t launch_wgrad_frag(hipStream_t st, int H, bool bf16, int64_t E, const void* a1_pk, const void* gz2_pk,
                           float* partial, float* gW2);
+
+// The same gradient with a1 = silu(P[dst] + Q[col] + d2*w1d) recomputed from the bf16-pair projected features
+// (edge_pairs() layouts only); the forward pass need not store a1 then.
+int32_t launch_wgrad_frag_recompute(hipStream_t st, int H, int64_t E, const int32_t* dst, const int32_t* col,
+                                    const float* d2, const void* PQ, const float* w1d, const void* gz2_pk,
+                                    float* partial, float* gW2);
 
 // out[i, 0..H) (row pitch ldo) = sum over t in ptr[i]:ptr[i+1] of X[perm ? perm[t] : t, :], X v-major (bf16 or
 // fp32), accumulated in fp32

@@ -74,7 +74,7 @@ __device__ __forceinline__ char* uoff(void* base, size_t bytes) { return reinter
 
 // 8 accumulator-mapped values of one half of a 32x32 block (column n of the tile, registers v = 8*vh .. 8*vh+7,
 // rows rbase + 8*(v>>2) + 4g + (v&3)): written row-major into the LDS tile and, operand-packed, to memory.
-// bf16 values are converted once.
+// bf16 values are converted once. packed == null: only the LDS tile is written.
 template <bool BF16, int STRIDE>
 __device__ __forceinline__ void emit_half(unsigned char* smem, int rbase, int g, int n, const float* vals, int vh,
                                           void* packed, size_t blk, int lane) {
@@ -91,7 +91,7 @@ __device__ __forceinline__ void emit_half(unsigned char* smem, int rbase, int g,
     {
       typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
       const u32x4_t w = {pk[0], pk[1], pk[2], pk[3]};
-      stg_nt<u32x4_t>(uoff(packed, (blk * 2 + vh) * 1024), lane * 16u, w);
+      if (packed) stg_nt<u32x4_t>(uoff(packed, (blk * 2 + vh) * 1024), lane * 16u, w);
     }
   } else {
     float* s32 = reinterpret_cast<float*>(smem);
@@ -100,8 +100,10 @@ __device__ __forceinline__ void emit_half(unsigned char* smem, int rbase, int g,
     char* pb = uoff(packed, (blk * 4 + 2 * vh) * 1024);
     const f32x4_t w0 = {vals[0], vals[1], vals[2], vals[3]};
     const f32x4_t w1 = {vals[4], vals[5], vals[6], vals[7]};
-    stg_nt<f32x4_t>(pb, lane * 16u, w0);
-    stg_nt<f32x4_t>(pb, lane * 16u + 1024u, w1);
+    if (packed) {
+      stg_nt<f32x4_t>(pb, lane * 16u, w0);
+      stg_nt<f32x4_t>(pb, lane * 16u + 1024u, w1);
+    }
   }
 }
 
@@ -1014,6 +1016,183 @@ k_wgrad_frag(int64_t nblk32, const void* __restrict__ a1_pk, const void* __restr
       }
 }
 
+
+// The same weight gradient with a1 = silu(z1) recomputed from the projected node features instead of read back
+// (bf16 pairs, H = 256 only): the forward pass then never stores a1, and this kernel trades its idle vector units
+// for half of its memory traffic. Per 16-edge chunk a wavefront gathers P[dst] and Q[col] for its four column
+// blocks (two pair words per row), forms the four A operands in registers, and multiplies them with the g_z2
+// operands streamed as before. Stages are software-pipelined with fixed register buffers: destination / source
+// indices two chunks ahead, gathers one chunk ahead, g_z2 three chunks ahead.
+struct WgradRcArgs {
+  int64_t blk0;      // first 32-edge block of this launch
+  int64_t nblk32;    // number of blocks of this launch
+  int E;
+  const int32_t *dst, *col;
+  const float* d2;
+  const void* PQ;
+  const float* w1d;
+  const void* gz2_pk;
+  float* partial;
+};
+
+// CHECK: the blocks of this launch may reach past the last edge (only the launch for the ragged last block)
+template <int H, bool CHECK>
+__global__ void __launch_bounds__(256) k_wgrad_frag_rc(WgradRcArgs p) {
+  constexpr int NCB = H / 32;
+  constexpr int NBW = NCB / 2;   // 32-blocks per wavefront along each output dimension (4)
+  constexpr int NPG = NBW / 2;   // pair words per gathered row and wavefront (2)
+  static_assert(H == 256, "pair storage");
+  using PQP = PQPitch<H, true>;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+  const int wa = wave >> 1, wb = wave & 1;
+  const int g = lane >> 5, x = lane & 31;
+  f32x16_t acc[NBW][NBW];
+#pragma unroll
+  for (int i = 0; i < NBW; ++i)
+#pragma unroll
+    for (int j = 0; j < NBW; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+  float w1d[NBW];
+#pragma unroll
+  for (int i = 0; i < NBW; ++i) w1d[i] = p.w1d[(wa * NBW + i) * 32 + x];
+  const int G = gridDim.x;
+  const int nblk = (int)p.nblk32, blk0 = (int)p.blk0;
+  const int nmine = nblk > (int)blockIdx.x ? (nblk - (int)blockIdx.x + G - 1) / G : 0;
+  const int nchunk = nmine * 2;   // two 16-edge chunks per 32-edge block; a multiple of 4 unless CHECK
+  const int E = p.E;
+  const unsigned colb = (unsigned)(wa * NPG * 32 + x) * 4u;   // this lane's first pair word inside a row
+  typedef int i32x4_t __attribute__((ext_vector_type(4)));
+
+  // chunk c (clamped to this workgroup's last chunk): its 32-edge block, and the first edge of this lane's two
+  // groups of four consecutive edges
+#define HGNN_RC_CC(c) ((c) < nchunk ? (c) : nchunk - 1)
+#define HGNN_RC_BLK(cc) (blk0 + (int)blockIdx.x + ((cc) >> 1) * G)
+#define HGNN_RC_E0(cc) (HGNN_RC_BLK(cc) * 32 + ((cc) & 1) * 16 + 4 * g)
+  // indices of the 8 edges (CHECK: zeros past the last edge; row 0 is always a valid row)
+#define HGNN_RC_IDX(c, di, ci)                                                                         \
+  {                                                                                                    \
+    const int cc_ = HGNN_RC_CC(c);                                                                     \
+    const int e0_ = HGNN_RC_E0(cc_);                                                                   \
+    _Pragma("unroll") for (int h = 0; h < 2; ++h) {                                                    \
+      const int e_ = e0_ + 8 * h;                                                                      \
+      i32x4_t a_ = {0, 0, 0, 0}, b_ = {0, 0, 0, 0};                                                    \
+      if (!CHECK || e_ + 3 < E) {                                                                      \
+        a_ = ldg_at<i32x4_t>(p.dst, (unsigned)e_ * 4u);                                                \
+        b_ = ldg_at<i32x4_t>(p.col, (unsigned)e_ * 4u);                                                \
+      } else {                                                                                         \
+        if (e_ < E) { a_[0] = p.dst[e_]; b_[0] = p.col[e_]; }                                          \
+        if (e_ + 1 < E) { a_[1] = p.dst[e_ + 1]; b_[1] = p.col[e_ + 1]; }                              \
+        if (e_ + 2 < E) { a_[2] = p.dst[e_ + 2]; b_[2] = p.col[e_ + 2]; }                              \
+      }                                                                                                \
+      _Pragma("unroll") for (int k = 0; k < 4; ++k) { di[4 * h + k] = a_[k]; ci[4 * h + k] = b_[k]; }  \
+    }                                                                                                  \
+  }
+  // gathers of chunk c: pair words of P and Q, and d2
+#define HGNN_RC_GATHER(c, di, ci, wp, wq, dd)                                                          \
+  {                                                                                                    \
+    const int cc_ = HGNN_RC_CC(c);                                                                     \
+    const int e0_ = HGNN_RC_E0(cc_);                                                                   \
+    _Pragma("unroll") for (int h = 0; h < 2; ++h) {                                                    \
+      const int e_ = e0_ + 8 * h;                                                                      \
+      f32x4_t d_ = {0.f, 0.f, 0.f, 0.f};                                                               \
+      if (!CHECK || e_ + 3 < E) d_ = ldg_at<f32x4_t>(p.d2, (unsigned)e_ * 4u);                         \
+      else {                                                                                           \
+        if (e_ < E) d_[0] = p.d2[e_];                                                                  \
+        if (e_ + 1 < E) d_[1] = p.d2[e_ + 1];                                                          \
+        if (e_ + 2 < E) d_[2] = p.d2[e_ + 2];                                                          \
+      }                                                                                                \
+      _Pragma("unroll") for (int k = 0; k < 4; ++k) dd[4 * h + k] = d_[k];                             \
+    }                                                                                                  \
+    _Pragma("unroll") for (int u = 0; u < 8; ++u) _Pragma("unroll") for (int pg = 0; pg < NPG; ++pg) { \
+      wp[u][pg] = ldg_u32(p.PQ, (unsigned)di[u] * PQP::ROW + colb + pg * 128u);                        \
+      wq[u][pg] = ldg_u32(p.PQ, (unsigned)ci[u] * PQP::ROW + colb + pg * 128u + PQP::QOFF);            \
+    }                                                                                                  \
+  }
+  // g_z2 operands of chunk c
+#define HGNN_RC_LOADB(c, b)                                                                            \
+  {                                                                                                    \
+    const int cc_ = HGNN_RC_CC(c);                                                                     \
+    const size_t eb_ = (size_t)HGNN_RC_BLK(cc_);                                                       \
+    _Pragma("unroll") for (int j = 0; j < NBW; ++j)                                                    \
+      b[j] = ldg_nt<bf16x8_t>(uoff(p.gz2_pk, (((eb_ * NCB + wb * NBW + j) * 2 + (cc_ & 1)) * 1024)), lane * 16u); \
+  }
+  // A operands from the gathered words, then the products (CHECK: A is zeroed for chunks past the end)
+#define HGNN_RC_MMA(c, wp, wq, dd, b)                                                                  \
+  {                                                                                                    \
+    const bool ok_ = !CHECK || (c) < nchunk;                                                           \
+    _Pragma("unroll") for (int i = 0; i < NBW; ++i) {                                                  \
+      float v_[8];                                                                                     \
+      _Pragma("unroll") for (int u = 0; u < 8; ++u) {                                                  \
+        const unsigned a_ = wp[u][i >> 1], q_ = wq[u][i >> 1];                                         \
+        const float z_ = ((i & 1) ? __uint_as_float(a_ & 0xffff0000u) + __uint_as_float(q_ & 0xffff0000u) \
+                                  : __uint_as_float(a_ << 16) + __uint_as_float(q_ << 16)) + dd[u] * w1d[i]; \
+        v_[u] = ok_ ? silu_f(z_) : 0.f;                                                                \
+      }                                                                                                \
+      typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));                                    \
+      const u32x4_t w_ = {pack_bf16x2(v_[0], v_[1]), pack_bf16x2(v_[2], v_[3]), pack_bf16x2(v_[4], v_[5]), \
+                          pack_bf16x2(v_[6], v_[7])};                                                  \
+      const bf16x8_t az_ = __builtin_bit_cast(bf16x8_t, w_);                                           \
+      _Pragma("unroll") for (int j = 0; j < NBW; ++j)                                                  \
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(az_, b[j], acc[i][j], 0, 0, 0);          \
+    }                                                                                                  \
+  }
+  if (nchunk > 0) {
+    int diA[8], ciA[8], diB[8], ciB[8];
+    unsigned wpA[8][NPG], wqA[8][NPG], wpB[8][NPG], wqB[8][NPG];
+    float ddA[8], ddB[8];
+    bf16x8_t b0[NBW], b1[NBW], b2[NBW], b3[NBW];
+    // prologue: indices of chunks 0 and 1, gathers of chunk 0, g_z2 of chunks 0..2
+    HGNN_RC_IDX(0, diA, ciA)
+    HGNN_RC_IDX(1, diB, ciB)
+    HGNN_RC_LOADB(0, b0)
+    HGNN_RC_LOADB(1, b1)
+    HGNN_RC_LOADB(2, b2)
+    HGNN_RC_GATHER(0, diA, ciA, wpA, wqA, ddA)
+    for (int c = 0; c < nchunk; c += 4) {
+      // chunk c (buffers A / b0)
+      HGNN_RC_GATHER(c + 1, diB, ciB, wpB, wqB, ddB)
+      HGNN_RC_IDX(c + 2, diA, ciA)
+      HGNN_RC_LOADB(c + 3, b3)
+      HGNN_RC_MMA(c, wpA, wqA, ddA, b0)
+      // chunk c + 1 (buffers B / b1)
+      HGNN_RC_GATHER(c + 2, diA, ciA, wpA, wqA, ddA)
+      HGNN_RC_IDX(c + 3, diB, ciB)
+      HGNN_RC_LOADB(c + 4, b0)
+      HGNN_RC_MMA(c + 1, wpB, wqB, ddB, b1)
+      // chunk c + 2 (buffers A / b2)
+      HGNN_RC_GATHER(c + 3, diB, ciB, wpB, wqB, ddB)
+      HGNN_RC_IDX(c + 4, diA, ciA)
+      HGNN_RC_LOADB(c + 5, b1)
+      HGNN_RC_MMA(c + 2, wpA, wqA, ddA, b2)
+      // chunk c + 3 (buffers B / b3)
+      HGNN_RC_GATHER(c + 4, diA, ciA, wpA, wqA, ddA)
+      HGNN_RC_IDX(c + 5, diB, ciB)
+      HGNN_RC_LOADB(c + 6, b2)
+      HGNN_RC_MMA(c + 3, wpB, wqB, ddB, b3)
+    }
+  }
+#undef HGNN_RC_CC
+#undef HGNN_RC_BLK
+#undef HGNN_RC_E0
+#undef HGNN_RC_IDX
+#undef HGNN_RC_GATHER
+#undef HGNN_RC_LOADB
+#undef HGNN_RC_MMA
+  float* out = p.partial + (size_t)blockIdx.x * H * H;
+#pragma unroll
+  for (int i = 0; i < NBW; ++i)
+#pragma unroll
+    for (int j = 0; j < NBW; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int k1 = (wa * NBW + i) * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+        const int k2 = (wb * NBW + j) * 32 + (lane & 31);
+        out[k1 * H + k2] = acc[i][j][v];
+      }
+}
+
 constexpr int WGRAD_FRAG_MAX_GRID = 512;
 size_t wgrad_frag_partial_floats(int H) { return (size_t)WGRAD_FRAG_MAX_GRID * H * H; }
 
@@ -1045,6 +1224,45 @@ int32_t launch_wgrad_frag(hipStream_t st, int H, bool bf16, int64_t E, const voi
                           : launch_wgrad_frag_t<256, false>(st, E, a1_pk, gz2_pk, partial, gW2);
   }
   return set_error(HGNN_ERR_BAD_SHAPE, "H must be 64, 128 or 256 (got %d)", H);
+}
+
+int32_t launch_wgrad_frag_recompute(hipStream_t st, int H, int64_t E, const int32_t* dst, const int32_t* col,
+                                    const float* d2, const void* PQ, const float* w1d, const void* gz2_pk,
+                                    float* partial, float* gW2) {
+  HGNN_REQUIRE(H == 256, HGNN_ERR_BAD_SHAPE, "the recomputing weight-gradient kernel needs bf16 pairs (H = 256)");
+  HGNN_REQUIRE(E >= 0 && E <= EDGE_MAX_E, HGNN_ERR_BAD_SHAPE, "edge kernels index edges with 32 bits (E = %lld)",
+               (long long)E);
+  // The branch-free kernel takes the same even number of whole 32-edge blocks per workgroup; the blocks left over
+  // (fewer than two per workgroup, and the ragged last one) go to a second launch of the checking variant, two
+  // blocks per workgroup. Every workgroup of both launches leaves one partial.
+  const int64_t nfull = E / 32, ntail = (E % 32) ? 1 : 0;
+  int64_t grid = num_cus();
+  if (grid > WGRAD_FRAG_MAX_GRID / 2) grid = WGRAD_FRAG_MAX_GRID / 2;
+  const int64_t per = (nfull / grid) & ~(int64_t)1;
+  const int64_t nmain = per * grid;
+  const int64_t nrest = nfull - nmain + ntail;
+  int64_t grid2 = (nrest + 1) / 2;
+  if (per == 0) grid = 0;
+  if (grid + grid2 == 0) grid2 = 1;   // E == 0: one workgroup writes a zero partial
+  WgradRcArgs a;
+  a.E = (int)E; a.dst = dst; a.col = col; a.d2 = d2; a.PQ = PQ; a.w1d = w1d;
+  a.gz2_pk = gz2_pk;
+  {
+    ProfScope ps(PT_WGRAD_EDGE, st);
+    if (grid > 0) {
+      a.blk0 = 0; a.nblk32 = nmain; a.partial = partial;
+      k_wgrad_frag_rc<256, false><<<dim3((unsigned)grid), 256, 0, st>>>(a);
+      HGNN_LAUNCH_CHECK("k_wgrad_frag_rc");
+    }
+    if (grid2 > 0) {
+      a.blk0 = nmain; a.nblk32 = nrest; a.partial = partial + (size_t)grid * H * H;
+      k_wgrad_frag_rc<256, true><<<dim3((unsigned)grid2), 256, 0, st>>>(a);
+      HGNN_LAUNCH_CHECK("k_wgrad_frag_rc");
+    }
+  }
+  const int nparts = (int)(grid + grid2);
+  float* dest[4] = {gW2, nullptr, nullptr, nullptr};
+  return launch_reduce_partials(st, partial, nparts, 1, (long)H * H, dest, 1, 0);
 }
 
 }  // namespace hgnn

@@ -34,7 +34,8 @@ struct LayerOff {  // element offsets into the flat weight buffer
 struct LayerSaved {
   float* PQ;    // [N,2H] fp32  P = h W1a + b1 | Q = h W1b   (or the same as bf16 pairs, [N,H] words)
   void* z2_vm;  // [E32,H] z2, v-major fragment order (bf16 or fp32)
-  void* a1_pk;  // [E32,H] silu(z1), operand-packed fragment order (bf16 or fp32)
+  void* a1_pk;  // [E32,H] silu(z1), operand-packed fragment order (bf16 or fp32); null with bf16 pairs, where the
+                // reverse pass recomputes it
   float* M;     // [N,H]
   float* z3;    // [N,H]
   size_t bytes;
@@ -46,7 +47,7 @@ static LayerSaved carve_saved(void* p, int N, int64_t E, int H, bool bf16) {
   const size_t eb = frag_rows(E) * H * (bf16 ? 2 : 4);
   s.PQ = c.take<float>((size_t)N * 2 * H);
   s.z2_vm = c.take<char>(eb);
-  s.a1_pk = c.take<char>(eb);
+  s.a1_pk = edge_pairs(H, bf16) ? nullptr : c.take<char>(eb);
   s.M = c.take<float>((size_t)N * H);
   s.z3 = c.take<float>((size_t)N * H);
   s.bytes = c.used();
@@ -323,7 +324,11 @@ extern "C" int32_t hgnn_mp_layer_bwd(void* stream, int32_t N, int64_t E, int32_t
   }
   HGNN_TRY(stream_after(sx, st, ss.ev[2]));
   // side: g_W2 = a1^T g_z2 streams while the main stream runs the two segment sums
-  HGNN_TRY(launch_wgrad_frag(sx, H, bf16, E, s.a1_pk, w.gz2_pk, w.partial2, gW + o.W2));
+  if (edge_pairs(H, bf16))
+    HGNN_TRY(launch_wgrad_frag_recompute(sx, H, E, dst, col, d2, s.PQ, W + o.W1 + 2 * HH, w.gz2_pk, w.partial2,
+                                         gW + o.W2));
+  else
+    HGNN_TRY(launch_wgrad_frag(sx, H, bf16, E, s.a1_pk, w.gz2_pk, w.partial2, gW + o.W2));
   HGNN_TRY(launch_segsum_vm(st, H, bf16, N, row_ptr, nullptr, w.gz1_vm, w.g_PQ, 2 * H, PT_SEGSUM_DST));     // g_P
   HGNN_TRY(launch_segsum_vm(st, H, bf16, N, colT_ptr, permT, w.gz1_vm, w.g_PQ + H, 2 * H, PT_SEGSUM_SRC));  // g_Q
   HGNN_TRY(stream_after(sx, st, ss.ev[3]));
