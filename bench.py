@@ -30,11 +30,14 @@ def kernel_work(tag, N, E, H, dtype):
     tensors it gathers counted once (compulsory traffic; re-reads are cache traffic)."""
     b = 2 if dtype == "bf16" else 4
     EH, NH = float(E) * H, float(N) * H
-    if tag == "edge_fused_fwd":      # out: a1, z2; in: dst, col, d2; gathers P|Q
-        return 2.0 * EH * H, 2 * EH * b + 12.0 * E + 2 * NH * b
+    pairs = dtype == "bf16" and H == 256   # a1 is recomputed in the reverse pass instead of stored
+    if tag == "edge_fused_fwd":      # out: z2 (and a1 unless recomputed); in: dst, col, d2; gathers P|Q
+        return 2.0 * EH * H, (1 if pairs else 2) * EH * b + 12.0 * E + 2 * NH * b
     if tag == "edge_fused_bwd":      # in: z2, dst, col, d2, c; out: g_z2, g_z1; gathers P|Q, g_M
         return 4.0 * EH * H, 3 * EH * b + 16.0 * E + 3 * NH * b
-    if tag == "wgrad_edge":          # in: a1, g_z2; out: H x H
+    if tag == "wgrad_edge":          # in: g_z2 and a1 (or dst, col, d2 and gathers of P|Q to recompute a1); out: H x H
+        if pairs:
+            return 2.0 * EH * H, EH * b + 12.0 * E + 2 * NH * b + 4.0 * H * H
         return 2.0 * EH * H, 2 * EH * b + 4.0 * H * H
     if tag == "seg_fwd":             # in: z2, rvec, row_ptr; out: M, v
         return 0.0, EH * b + 12.0 * E + 4.0 * (N + 1) + (NH + 6.0 * N) * 4

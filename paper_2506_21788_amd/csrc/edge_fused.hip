@@ -1019,9 +1019,9 @@ k_wgrad_frag(int64_t nblk32, const void* __restrict__ a1_pk, const void* __restr
 
 // The same weight gradient with a1 = silu(z1) recomputed from the projected node features instead of read back
 // (bf16 pairs, H = 256 only): the forward pass then never stores a1, and this kernel trades its idle vector units
-// for half of its memory traffic. Per 16-edge chunk a wavefront gathers P[dst] and Q[col] for its four column
-// blocks (two pair words per row), forms the four A operands in registers, and multiplies them with the g_z2
-// operands streamed as before. Stages are software-pipelined with fixed register buffers: destination / source
+// for half of its memory traffic. Per 16-edge chunk a wavefront gathers P[dst] and Q[col] for its own two column
+// blocks (one pair word per row), forms the two A operands in registers, and multiplies them with all eight g_z2
+// operands of the chunk (each wavefront reads them; three of the four reads are cache hits). Stages are software-pipelined with fixed register buffers: destination / source
 // indices two chunks ahead, gathers one chunk ahead, g_z2 three chunks ahead.
 struct WgradRcArgs {
   int64_t blk0;      // first 32-edge block of this launch
@@ -1039,30 +1039,29 @@ struct WgradRcArgs {
 template <int H, bool CHECK>
 __global__ void __launch_bounds__(256) k_wgrad_frag_rc(WgradRcArgs p) {
   constexpr int NCB = H / 32;
-  constexpr int NBW = NCB / 2;   // 32-blocks per wavefront along each output dimension (4)
-  constexpr int NPG = NBW / 2;   // pair words per gathered row and wavefront (2)
+  constexpr int NBA = 2;         // A blocks per wavefront: one pair word per gathered row, recomputed by this wavefront only
+  constexpr int NBB = NCB;       // every wavefront multiplies them with all column blocks of g_z2
   static_assert(H == 256, "pair storage");
   using PQP = PQPitch<H, true>;
   const int lane = threadIdx.x & 63;
-  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-  const int wa = wave >> 1, wb = wave & 1;
+  const int wa = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
   const int g = lane >> 5, x = lane & 31;
-  f32x16_t acc[NBW][NBW];
+  f32x16_t acc[NBA][NBB];
 #pragma unroll
-  for (int i = 0; i < NBW; ++i)
+  for (int i = 0; i < NBA; ++i)
 #pragma unroll
-    for (int j = 0; j < NBW; ++j)
+    for (int j = 0; j < NBB; ++j)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-  float w1d[NBW];
+  float w1d[NBA];
 #pragma unroll
-  for (int i = 0; i < NBW; ++i) w1d[i] = p.w1d[(wa * NBW + i) * 32 + x];
+  for (int i = 0; i < NBA; ++i) w1d[i] = p.w1d[(wa * NBA + i) * 32 + x];
   const int G = gridDim.x;
   const int nblk = (int)p.nblk32, blk0 = (int)p.blk0;
   const int nmine = nblk > (int)blockIdx.x ? (nblk - (int)blockIdx.x + G - 1) / G : 0;
   const int nchunk = nmine * 2;   // two 16-edge chunks per 32-edge block; a multiple of 4 unless CHECK
   const int E = p.E;
-  const unsigned colb = (unsigned)(wa * NPG * 32 + x) * 4u;   // this lane's first pair word inside a row
+  const unsigned colb = (unsigned)(wa * 32 + x) * 4u;   // this lane's pair word inside a row
   typedef int i32x4_t __attribute__((ext_vector_type(4)));
 
   // chunk c (clamped to this workgroup's last chunk): its 32-edge block, and the first edge of this lane's two
@@ -1105,9 +1104,9 @@ __global__ void __launch_bounds__(256) k_wgrad_frag_rc(WgradRcArgs p) {
       }                                                                                                \
       _Pragma("unroll") for (int k = 0; k < 4; ++k) dd[4 * h + k] = d_[k];                             \
     }                                                                                                  \
-    _Pragma("unroll") for (int u = 0; u < 8; ++u) _Pragma("unroll") for (int pg = 0; pg < NPG; ++pg) { \
-      wp[u][pg] = ldg_u32(p.PQ, (unsigned)di[u] * PQP::ROW + colb + pg * 128u);                        \
-      wq[u][pg] = ldg_u32(p.PQ, (unsigned)ci[u] * PQP::ROW + colb + pg * 128u + PQP::QOFF);            \
+    _Pragma("unroll") for (int u = 0; u < 8; ++u) {                                                    \
+      wp[u] = ldg_u32(p.PQ, (unsigned)di[u] * PQP::ROW + colb);                                        \
+      wq[u] = ldg_u32(p.PQ, (unsigned)ci[u] * PQP::ROW + colb + PQP::QOFF);                            \
     }                                                                                                  \
   }
   // g_z2 operands of chunk c
@@ -1115,17 +1114,17 @@ __global__ void __launch_bounds__(256) k_wgrad_frag_rc(WgradRcArgs p) {
   {                                                                                                    \
     const int cc_ = HGNN_RC_CC(c);                                                                     \
     const size_t eb_ = (size_t)HGNN_RC_BLK(cc_);                                                       \
-    _Pragma("unroll") for (int j = 0; j < NBW; ++j)                                                    \
-      b[j] = ldg_nt<bf16x8_t>(uoff(p.gz2_pk, (((eb_ * NCB + wb * NBW + j) * 2 + (cc_ & 1)) * 1024)), lane * 16u); \
+    _Pragma("unroll") for (int j = 0; j < NBB; ++j)                                                    \
+      b[j] = ldg_at<bf16x8_t>(uoff(p.gz2_pk, (((eb_ * NCB + j) * 2 + (cc_ & 1)) * 1024)), lane * 16u); \
   }
   // A operands from the gathered words, then the products (CHECK: A is zeroed for chunks past the end)
 #define HGNN_RC_MMA(c, wp, wq, dd, b)                                                                  \
   {                                                                                                    \
     const bool ok_ = !CHECK || (c) < nchunk;                                                           \
-    _Pragma("unroll") for (int i = 0; i < NBW; ++i) {                                                  \
+    _Pragma("unroll") for (int i = 0; i < NBA; ++i) {                                                  \
       float v_[8];                                                                                     \
       _Pragma("unroll") for (int u = 0; u < 8; ++u) {                                                  \
-        const unsigned a_ = wp[u][i >> 1], q_ = wq[u][i >> 1];                                         \
+        const unsigned a_ = wp[u], q_ = wq[u];                                                         \
         const float z_ = ((i & 1) ? __uint_as_float(a_ & 0xffff0000u) + __uint_as_float(q_ & 0xffff0000u) \
                                   : __uint_as_float(a_ << 16) + __uint_as_float(q_ << 16)) + dd[u] * w1d[i]; \
         v_[u] = ok_ ? silu_f(z_) : 0.f;                                                                \
@@ -1134,15 +1133,15 @@ __global__ void __launch_bounds__(256) k_wgrad_frag_rc(WgradRcArgs p) {
       const u32x4_t w_ = {pack_bf16x2(v_[0], v_[1]), pack_bf16x2(v_[2], v_[3]), pack_bf16x2(v_[4], v_[5]), \
                           pack_bf16x2(v_[6], v_[7])};                                                  \
       const bf16x8_t az_ = __builtin_bit_cast(bf16x8_t, w_);                                           \
-      _Pragma("unroll") for (int j = 0; j < NBW; ++j)                                                  \
+      _Pragma("unroll") for (int j = 0; j < NBB; ++j)                                                  \
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(az_, b[j], acc[i][j], 0, 0, 0);          \
     }                                                                                                  \
   }
   if (nchunk > 0) {
     int diA[8], ciA[8], diB[8], ciB[8];
-    unsigned wpA[8][NPG], wqA[8][NPG], wpB[8][NPG], wqB[8][NPG];
+    unsigned wpA[8], wqA[8], wpB[8], wqB[8];
     float ddA[8], ddB[8];
-    bf16x8_t b0[NBW], b1[NBW], b2[NBW], b3[NBW];
+    bf16x8_t b0[NBB], b1[NBB], b2[NBB], b3[NBB];
     // prologue: indices of chunks 0 and 1, gathers of chunk 0, g_z2 of chunks 0..2
     HGNN_RC_IDX(0, diA, ciA)
     HGNN_RC_IDX(1, diB, ciB)
@@ -1182,13 +1181,13 @@ __global__ void __launch_bounds__(256) k_wgrad_frag_rc(WgradRcArgs p) {
 #undef HGNN_RC_MMA
   float* out = p.partial + (size_t)blockIdx.x * H * H;
 #pragma unroll
-  for (int i = 0; i < NBW; ++i)
+  for (int i = 0; i < NBA; ++i)
 #pragma unroll
-    for (int j = 0; j < NBW; ++j)
+    for (int j = 0; j < NBB; ++j)
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        const int k1 = (wa * NBW + i) * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-        const int k2 = (wb * NBW + j) * 32 + (lane & 31);
+        const int k1 = (wa * NBA + i) * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+        const int k2 = j * 32 + (lane & 31);
         out[k1 * H + k2] = acc[i][j][v];
       }
 }
