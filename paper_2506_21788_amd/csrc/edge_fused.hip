@@ -1021,8 +1021,9 @@ k_wgrad_frag(int64_t nblk32, const void* __restrict__ a1_pk, const void* __restr
 // (bf16 pairs, H = 256 only): the forward pass then never stores a1, and this kernel trades its idle vector units
 // for half of its memory traffic. Per 16-edge chunk a wavefront gathers P[dst] and Q[col] for its own two column
 // blocks (one pair word per row), forms the two A operands in registers, and multiplies them with all eight g_z2
-// operands of the chunk (each wavefront reads them; three of the four reads are cache hits). Stages are software-pipelined with fixed register buffers: destination / source
-// indices two chunks ahead, gathers one chunk ahead, g_z2 three chunks ahead.
+// operands of the chunk. Those are loaded once per workgroup (two blocks per wavefront) and shared through a ring
+// of LDS stages. Everything is software-pipelined with fixed register rings: g_z2 four chunks ahead, gathers three
+// chunks ahead, the edge indices they need one chunk before that; one barrier per chunk publishes the next stage.
 struct WgradRcArgs {
   int64_t blk0;      // first 32-edge block of this launch
   int64_t nblk32;    // number of blocks of this launch
@@ -1035,14 +1036,18 @@ struct WgradRcArgs {
   float* partial;
 };
 
-// CHECK: the blocks of this launch may reach past the last edge (only the launch for the ragged last block)
+// CHECK: the blocks of this launch may reach past the last edge, and a workgroup's chunk count need not be a
+// multiple of four (only the launch for the left-over blocks)
 template <int H, bool CHECK>
 __global__ void __launch_bounds__(256) k_wgrad_frag_rc(WgradRcArgs p) {
   constexpr int NCB = H / 32;
-  constexpr int NBA = 2;         // A blocks per wavefront: one pair word per gathered row, recomputed by this wavefront only
+  constexpr int NBA = 2;         // A blocks per wavefront, recomputed by this wavefront only
   constexpr int NBB = NCB;       // every wavefront multiplies them with all column blocks of g_z2
+  constexpr int NBL = NCB / 4;   // g_z2 blocks each wavefront loads for the workgroup
+  constexpr int NSTAGE = 4;
   static_assert(H == 256, "pair storage");
   using PQP = PQPitch<H, true>;
+  __shared__ __align__(16) unsigned char stage[NSTAGE * NCB * 1024];
   const int lane = threadIdx.x & 63;
   const int wa = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
   const int g = lane >> 5, x = lane & 31;
@@ -1109,18 +1114,25 @@ __global__ void __launch_bounds__(256) k_wgrad_frag_rc(WgradRcArgs p) {
       wq[u] = ldg_u32(p.PQ, (unsigned)ci[u] * PQP::ROW + colb + PQP::QOFF);                            \
     }                                                                                                  \
   }
-  // g_z2 operands of chunk c
+  // this wavefront's share of the g_z2 operands of chunk c: memory -> registers, registers -> LDS stage
 #define HGNN_RC_LOADB(c, b)                                                                            \
   {                                                                                                    \
     const int cc_ = HGNN_RC_CC(c);                                                                     \
     const size_t eb_ = (size_t)HGNN_RC_BLK(cc_);                                                       \
-    _Pragma("unroll") for (int j = 0; j < NBB; ++j)                                                    \
-      b[j] = ldg_at<bf16x8_t>(uoff(p.gz2_pk, (((eb_ * NCB + j) * 2 + (cc_ & 1)) * 1024)), lane * 16u); \
+    _Pragma("unroll") for (int j = 0; j < NBL; ++j)                                                    \
+      b[j] = ldg_nt<bf16x8_t>(uoff(p.gz2_pk, (((eb_ * NCB + wa * NBL + j) * 2 + (cc_ & 1)) * 1024)), lane * 16u); \
   }
-  // A operands from the gathered words, then the products (CHECK: A is zeroed for chunks past the end)
-#define HGNN_RC_MMA(c, wp, wq, dd, b)                                                                  \
+#define HGNN_RC_STAGEB(st, b)                                                                          \
+  _Pragma("unroll") for (int j = 0; j < NBL; ++j)                                                      \
+    *reinterpret_cast<bf16x8_t*>(stage + ((st) * NCB + wa * NBL + j) * 1024 + lane * 16) = b[j];
+  // A operands from the gathered words, all g_z2 operands of the chunk from its LDS stage, then the products
+  // (CHECK: A is zeroed for chunks past the end)
+#define HGNN_RC_MMA(c, st, wp, wq, dd)                                                                 \
   {                                                                                                    \
     const bool ok_ = !CHECK || (c) < nchunk;                                                           \
+    bf16x8_t b_[NBB];                                                                                  \
+    _Pragma("unroll") for (int j = 0; j < NBB; ++j)                                                    \
+      b_[j] = *reinterpret_cast<const bf16x8_t*>(stage + ((st) * NCB + j) * 1024 + lane * 16);         \
     _Pragma("unroll") for (int i = 0; i < NBA; ++i) {                                                  \
       float v_[8];                                                                                     \
       _Pragma("unroll") for (int u = 0; u < 8; ++u) {                                                  \
@@ -1134,42 +1146,44 @@ __global__ void __launch_bounds__(256) k_wgrad_frag_rc(WgradRcArgs p) {
                           pack_bf16x2(v_[6], v_[7])};                                                  \
       const bf16x8_t az_ = __builtin_bit_cast(bf16x8_t, w_);                                           \
       _Pragma("unroll") for (int j = 0; j < NBB; ++j)                                                  \
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(az_, b[j], acc[i][j], 0, 0, 0);          \
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(az_, b_[j], acc[i][j], 0, 0, 0);         \
     }                                                                                                  \
   }
-  if (nchunk > 0) {
-    int diA[8], ciA[8], diB[8], ciB[8];
-    unsigned wpA[8], wqA[8], wpB[8], wqB[8];
-    float ddA[8], ddB[8];
-    bf16x8_t b0[NBB], b1[NBB], b2[NBB], b3[NBB];
-    // prologue: indices of chunks 0 and 1, gathers of chunk 0, g_z2 of chunks 0..2
-    HGNN_RC_IDX(0, diA, ciA)
-    HGNN_RC_IDX(1, diB, ciB)
+  // one pipeline step for chunk c with the ring slots named explicitly (k = c mod 4):
+  //   stage chunk c+1's g_z2, ask for chunk c+4's, gather chunk c+3, ask for the indices of chunk c+4,
+  //   barrier, multiply chunk c
+#define HGNN_RC_STEP(c, k, bN, bL, diG, ciG, diL, ciL, wpG, wqG, ddG, wpM, wqM, ddM)                   \
+  HGNN_RC_STAGEB(((k) + 1) & 3, bN)                                                                    \
+  HGNN_RC_LOADB((c) + 4, bL)                                                                           \
+  HGNN_RC_GATHER((c) + 3, diG, ciG, wpG, wqG, ddG)                                                     \
+  HGNN_RC_IDX((c) + 4, diL, ciL)                                                                       \
+  __syncthreads();                                                                                     \
+  HGNN_RC_MMA(c, k, wpM, wqM, ddM)
+  if (nchunk > 0) {   // uniform over the workgroup
+    int di0[8], ci0[8], di1[8], ci1[8];                       // index ring: slot = chunk mod 2
+    unsigned wp0[8], wq0[8], wp1[8], wq1[8], wp2[8], wq2[8], wp3[8], wq3[8];   // gather ring: slot = chunk mod 4
+    float dd0[8], dd1[8], dd2[8], dd3[8];
+    bf16x8_t b0[NBL], b1[NBL], b2[NBL], b3[NBL];              // g_z2 load ring: slot = chunk mod 4
+    // prologue: g_z2 of chunks 0..3, gathers of chunks 0..2, indices of chunk 3, chunk 0 staged
     HGNN_RC_LOADB(0, b0)
     HGNN_RC_LOADB(1, b1)
     HGNN_RC_LOADB(2, b2)
-    HGNN_RC_GATHER(0, diA, ciA, wpA, wqA, ddA)
+    HGNN_RC_LOADB(3, b3)
+    HGNN_RC_IDX(0, di0, ci0)
+    HGNN_RC_GATHER(0, di0, ci0, wp0, wq0, dd0)
+    HGNN_RC_IDX(1, di1, ci1)
+    HGNN_RC_GATHER(1, di1, ci1, wp1, wq1, dd1)
+    HGNN_RC_IDX(2, di0, ci0)
+    HGNN_RC_GATHER(2, di0, ci0, wp2, wq2, dd2)
+    HGNN_RC_IDX(3, di1, ci1)
+    HGNN_RC_STAGEB(0, b0)
+    __syncthreads();
     for (int c = 0; c < nchunk; c += 4) {
-      // chunk c (buffers A / b0)
-      HGNN_RC_GATHER(c + 1, diB, ciB, wpB, wqB, ddB)
-      HGNN_RC_IDX(c + 2, diA, ciA)
-      HGNN_RC_LOADB(c + 3, b3)
-      HGNN_RC_MMA(c, wpA, wqA, ddA, b0)
-      // chunk c + 1 (buffers B / b1)
-      HGNN_RC_GATHER(c + 2, diA, ciA, wpA, wqA, ddA)
-      HGNN_RC_IDX(c + 3, diB, ciB)
-      HGNN_RC_LOADB(c + 4, b0)
-      HGNN_RC_MMA(c + 1, wpB, wqB, ddB, b1)
-      // chunk c + 2 (buffers A / b2)
-      HGNN_RC_GATHER(c + 3, diB, ciB, wpB, wqB, ddB)
-      HGNN_RC_IDX(c + 4, diA, ciA)
-      HGNN_RC_LOADB(c + 5, b1)
-      HGNN_RC_MMA(c + 2, wpA, wqA, ddA, b2)
-      // chunk c + 3 (buffers B / b3)
-      HGNN_RC_GATHER(c + 4, diA, ciA, wpA, wqA, ddA)
-      HGNN_RC_IDX(c + 5, diB, ciB)
-      HGNN_RC_LOADB(c + 6, b2)
-      HGNN_RC_MMA(c + 3, wpB, wqB, ddB, b3)
+      //           chunk  k  stage-from load-into  gather idx      next idx     gather-into        multiply-from
+      HGNN_RC_STEP(c,     0, b1,        b0,        di1, ci1,       di0, ci0,    wp3, wq3, dd3,     wp0, wq0, dd0)
+      HGNN_RC_STEP(c + 1, 1, b2,        b1,        di0, ci0,       di1, ci1,    wp0, wq0, dd0,     wp1, wq1, dd1)
+      HGNN_RC_STEP(c + 2, 2, b3,        b2,        di1, ci1,       di0, ci0,    wp1, wq1, dd1,     wp2, wq2, dd2)
+      HGNN_RC_STEP(c + 3, 3, b0,        b3,        di0, ci0,       di1, ci1,    wp2, wq2, dd2,     wp3, wq3, dd3)
     }
   }
 #undef HGNN_RC_CC
@@ -1178,7 +1192,9 @@ __global__ void __launch_bounds__(256) k_wgrad_frag_rc(WgradRcArgs p) {
 #undef HGNN_RC_IDX
 #undef HGNN_RC_GATHER
 #undef HGNN_RC_LOADB
+#undef HGNN_RC_STAGEB
 #undef HGNN_RC_MMA
+#undef HGNN_RC_STEP
   float* out = p.partial + (size_t)blockIdx.x * H * H;
 #pragma unroll
   for (int i = 0; i < NBA; ++i)
