@@ -1068,11 +1068,17 @@ __global__ void __launch_bounds__(256) k_wgrad_frag_rc(WgradRcArgs p) {
   const int E = p.E;
   const unsigned colb = (unsigned)(wa * 32 + x) * 4u;   // this lane's pair word inside a row
   typedef int i32x4_t __attribute__((ext_vector_type(4)));
+  // Which blocks are this workgroup's: the main launch (every workgroup has the same count) gives each XCD
+  // (workgroups are dealt to the 8 XCDs round-robin) a contiguous eighth of the blocks, dealt round-robin inside
+  // the XCD, so that the node rows an XCD gathers stay in its own L2; otherwise plain round-robin.
+  const bool by_xcd = !CHECK && (G & 7) == 0;
+  const int bstride = by_xcd ? (G >> 3) : G;
+  const int bfirst = blk0 + (by_xcd ? ((int)blockIdx.x & 7) * (nmine * bstride) + ((int)blockIdx.x >> 3) : (int)blockIdx.x);
 
   // chunk c (clamped to this workgroup's last chunk): its 32-edge block, and the first edge of this lane's two
   // groups of four consecutive edges
 #define HGNN_RC_CC(c) ((c) < nchunk ? (c) : nchunk - 1)
-#define HGNN_RC_BLK(cc) (blk0 + (int)blockIdx.x + ((cc) >> 1) * G)
+#define HGNN_RC_BLK(cc) (bfirst + ((cc) >> 1) * bstride)
 #define HGNN_RC_E0(cc) (HGNN_RC_BLK(cc) * 32 + ((cc) & 1) * 16 + 4 * g)
   // indices of the 8 edges (CHECK: zeros past the last edge; row 0 is always a valid row)
 #define HGNN_RC_IDX(c, di, ci)                                                                         \
