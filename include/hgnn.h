@@ -122,6 +122,14 @@ int32_t hgnn_embed_bwd(void* stream, int32_t N, int32_t H, const int32_t* Z,
  * _bwd takes g_h_out = dL/dh', g_v_out = dL/dv' and writes g_h_in = dL/dh, g_v_in = dL/dv and gW.
  * d2 and rvec are constants of the step (no gradient with respect to positions).
  * h_out may not alias h_in; g_h_in may not alias g_h_out.
+ * Errors: BAD_SHAPE for H outside {64,128,256} or an unknown dtype; OVERFLOW if E > 2^31 - 129 or
+ * N * 2H * 4 bytes reaches 4 GiB (the edge kernels index edges and gathered rows with 32 bits);
+ * WORKSPACE_TOO_SMALL if ws / saved are smaller than the query says; UNIMPLEMENTED if saved == NULL.
+ * _bwd also enqueues weight-gradient work on a stream the library creates once (default priority). It
+ * forks from and joins `stream` through events inside the call, so for the caller everything is
+ * ordered on `stream`; the call that creates that stream must not run under stream capture. The
+ * environment variable HGNN_SIDE_STREAM=0 keeps all work on `stream`.
+ * The library keeps per-process state without locks: call it from one host thread at a time.
  * ------------------------------------------------------------------------------------------- */
 int32_t hgnn_mp_layer_workspace_bytes(int32_t N, int64_t E, int32_t H, int32_t dtype,
                                       size_t* ws_bytes_host, size_t* saved_bytes_host);
