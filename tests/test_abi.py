@@ -58,6 +58,20 @@ def test_host_side_argument_checks_need_no_gpu():
     rc = lib.hgnn_mp_layer_workspace_bytes(ctypes.c_int32(10), ctypes.c_int64(2 ** 31), ctypes.c_int32(128),
                                            ctypes.c_int32(0), ctypes.byref(a), ctypes.byref(s))
     assert rc == -7
+    # gathered node rows are addressed with 32-bit byte offsets: N * 2H * 4 bytes must stay below 4 GiB
+    rc = lib.hgnn_mp_layer_workspace_bytes(ctypes.c_int32(3_000_000), ctypes.c_int64(50), ctypes.c_int32(256),
+                                           ctypes.c_int32(1), ctypes.byref(a), ctypes.byref(s))
+    assert rc == -7 and b"4 GiB" in lib.hgnn_last_error_string()
+    rc = lib.hgnn_mp_layer_workspace_bytes(ctypes.c_int32(2_000_000), ctypes.c_int64(50), ctypes.c_int32(256),
+                                           ctypes.c_int32(1), ctypes.byref(a), ctypes.byref(s))
+    assert rc == 0
+    # with bf16 operands at H = 256 the reverse pass recomputes silu(z1): one [E,H] tensor less is saved
+    s16, s32 = ctypes.c_size_t(0), ctypes.c_size_t(0)
+    assert lib.hgnn_mp_layer_workspace_bytes(ctypes.c_int32(1000), ctypes.c_int64(32000), ctypes.c_int32(256),
+                                             ctypes.c_int32(1), ctypes.byref(a), ctypes.byref(s16)) == 0
+    assert lib.hgnn_mp_layer_workspace_bytes(ctypes.c_int32(1000), ctypes.c_int64(32000), ctypes.c_int32(256),
+                                             ctypes.c_int32(0), ctypes.byref(a), ctypes.byref(s32)) == 0
+    assert s16.value < 32000 * 256 * 2 * 2 <= s32.value
     # head width must equal H
     rc = lib.hgnn_multihead_decode_workspace_bytes(ctypes.c_int32(10), ctypes.c_int32(2), ctypes.c_int32(128),
                                                    ctypes.c_int32(64), ctypes.c_int32(2), ctypes.c_int32(0),
