@@ -554,7 +554,30 @@ k_seg_fwd_vm(int N, const int32_t* __restrict__ row_ptr, const void* __restrict_
   float acc[NV], tx[NV], ty[NV], tz[NV];
 #pragma unroll
   for (int c = 0; c < NV; ++c) acc[c] = tx[c] = ty[c] = tz[c] = 0.f;
-  for (int e = e0; e < e1; ++e) {
+  // a row's edges are summed in list order; four edges per trip so that their loads are in flight together
+  constexpr int EPT = 4;
+  int e = e0;
+  for (; e + EPT <= e1; e += EPT) {
+    float r[EPT][3], z[EPT][NV];
+#pragma unroll
+    for (int u = 0; u < EPT; ++u) {
+#pragma unroll
+      for (int k = 0; k < 3; ++k) r[u][k] = rvec[3 * (size_t)(e + u) + k];
+#pragma unroll
+      for (int c = 0; c < S::NPASS; ++c) S::fetch(z2_vm, (size_t)(e + u), c, hp, x, &z[u][c * S::PER]);
+    }
+#pragma unroll
+    for (int u = 0; u < EPT; ++u)
+#pragma unroll
+      for (int c = 0; c < NV; ++c) {
+        const float m = silu_f(z[u][c]);
+        acc[c] += m;
+        tx[c] += m * r[u][0];
+        ty[c] += m * r[u][1];
+        tz[c] += m * r[u][2];
+      }
+  }
+  for (; e < e1; ++e) {
     const float rx = rvec[3 * (size_t)e], ry = rvec[3 * (size_t)e + 1], rz = rvec[3 * (size_t)e + 2];
     float z[NV];
 #pragma unroll
@@ -623,19 +646,22 @@ k_segsum_vm(int N, const int32_t* __restrict__ ptr, const int32_t* __restrict__ 
 #pragma unroll
   for (int c = 0; c < NV; ++c) acc[c] = 0.f;
   int t = t0;
-  for (; t + 2 <= t1; t += 2) {   // two edges per trip: their loads are independent
-    const size_t ea = perm ? (size_t)perm[t] : (size_t)t;
-    const size_t eb = perm ? (size_t)perm[t + 1] : (size_t)(t + 1);
-    float va[NV], vb[NV];
+  constexpr int EPT = 4;
+  for (; t + EPT <= t1; t += EPT) {   // four edges per trip: their loads are independent; summed in list order
+    size_t ee[EPT];
 #pragma unroll
-    for (int c = 0; c < S::NPASS; ++c) {
-      S::fetch(X, ea, c, hp, x, &va[c * S::PER]);
-      S::fetch(X, eb, c, hp, x, &vb[c * S::PER]);
-    }
+    for (int u = 0; u < EPT; ++u) ee[u] = perm ? (size_t)perm[t + u] : (size_t)(t + u);
+    float vv[EPT][NV];
 #pragma unroll
-    for (int c = 0; c < NV; ++c) { acc[c] += va[c]; acc[c] += vb[c]; }
+    for (int u = 0; u < EPT; ++u)
+#pragma unroll
+      for (int c = 0; c < S::NPASS; ++c) S::fetch(X, ee[u], c, hp, x, &vv[u][c * S::PER]);
+#pragma unroll
+    for (int u = 0; u < EPT; ++u)
+#pragma unroll
+      for (int c = 0; c < NV; ++c) acc[c] += vv[u][c];
   }
-  if (t < t1) {
+  for (; t < t1; ++t) {
     const size_t ea = perm ? (size_t)perm[t] : (size_t)t;
     float va[NV];
 #pragma unroll
