@@ -127,10 +127,13 @@ int32_t hgnn_embed_bwd(void* stream, int32_t N, int32_t H, const int32_t* Z,
  * WORKSPACE_TOO_SMALL if ws / saved are smaller than the query says; UNIMPLEMENTED if saved == NULL.
  * _bwd also enqueues weight-gradient work on a stream the library creates once (default priority). It
  * forks from and joins `stream` through events inside the call, so for the caller everything is
- * ordered on `stream`; the call that creates that stream must not run under stream capture. The
- * environment variable HGNN_SIDE_STREAM=0 keeps all work on `stream`.
+ * ordered on `stream`; the call that creates that stream must not run under stream capture.
+ * hgnn_set_side_stream(0) (or the environment variable HGNN_SIDE_STREAM=0 before the first call) keeps all
+ * work on `stream`, e.g. to time kernels in isolation; it returns the previous setting (0 / 1).
  * The library keeps per-process state without locks: call it from one host thread at a time.
  * ------------------------------------------------------------------------------------------- */
+int32_t hgnn_set_side_stream(int32_t enable);
+
 int32_t hgnn_mp_layer_workspace_bytes(int32_t N, int64_t E, int32_t H, int32_t dtype,
                                       size_t* ws_bytes_host, size_t* saved_bytes_host);
 

@@ -20,7 +20,7 @@ EXPORTS = [
     "hgnn_last_error_string", "hgnn_version",
     "hgnn_radius_graph_workspace_bytes", "hgnn_radius_graph_count", "hgnn_radius_graph_fill",
     "hgnn_embed_fwd", "hgnn_embed_bwd", "hgnn_embed_bwd_workspace_bytes",
-    "hgnn_mp_layer_workspace_bytes", "hgnn_mp_layer_fwd", "hgnn_mp_layer_bwd",
+    "hgnn_set_side_stream", "hgnn_mp_layer_workspace_bytes", "hgnn_mp_layer_fwd", "hgnn_mp_layer_bwd",
     "hgnn_pool_by_graph_fwd", "hgnn_pool_by_graph_bwd",
     "hgnn_multihead_plan_ints", "hgnn_multihead_plan",
     "hgnn_multihead_decode_workspace_bytes", "hgnn_multihead_decode_fwd", "hgnn_multihead_decode_bwd",
@@ -86,6 +86,12 @@ def last_error_string() -> str:
 
 def version() -> int:
     return int(_lib.hgnn_version())
+
+
+def set_side_stream(enable: bool) -> bool:
+    """Weight gradients of the layer's reverse pass on the library's side stream (default) or not; returns the
+    previous setting."""
+    return bool(_lib.hgnn_set_side_stream(C.c_int32(1 if enable else 0)))
 
 
 def _check(code):

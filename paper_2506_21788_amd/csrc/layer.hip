@@ -112,6 +112,16 @@ static int32_t stream_after(hipStream_t to, hipStream_t from, hipEvent_t ev) {
   return HGNN_OK;
 }
 
+// -1: not decided yet (then the environment variable HGNN_SIDE_STREAM decides: "0" = off); 0 / 1: set by the caller
+static int g_side_mode = -1;
+static bool side_stream_enabled() {
+  if (g_side_mode < 0) {
+    const char* e = getenv("HGNN_SIDE_STREAM");
+    g_side_mode = (e && e[0] == '0') ? 0 : 1;
+  }
+  return g_side_mode != 0;
+}
+
 static int32_t check_layer_args(int N, int64_t E, int H, int dtype) {
   HGNN_REQUIRE(N >= 0 && E >= 0, HGNN_ERR_BAD_SHAPE, "negative N or E");
   HGNN_REQUIRE(E <= 2147483647LL - 128, HGNN_ERR_OVERFLOW, "edge count does not fit the 32-bit edge indices");
@@ -126,6 +136,12 @@ static int32_t check_layer_args(int N, int64_t E, int H, int dtype) {
 }  // namespace hgnn
 
 using namespace hgnn;
+
+extern "C" int32_t hgnn_set_side_stream(int32_t enable) {
+  const int32_t before = side_stream_enabled() ? 1 : 0;
+  g_side_mode = enable ? 1 : 0;
+  return before;
+}
 
 extern "C" int32_t hgnn_mp_layer_workspace_bytes(int32_t N, int64_t E, int32_t H, int32_t dtype,
                                                  size_t* ws_bytes_host, size_t* saved_bytes_host) {
@@ -252,9 +268,7 @@ extern "C" int32_t hgnn_mp_layer_bwd(void* stream, int32_t N, int64_t E, int32_t
 
   SideStream& ss = side_stream();
   HGNN_REQUIRE(ss.ok, HGNN_ERR_HIP, "could not create the side stream");
-  // HGNN_SIDE_STREAM=0 keeps everything on the caller's stream (for timing kernels in isolation)
-  static const bool use_side = [] { const char* e = getenv("HGNN_SIDE_STREAM"); return !(e && e[0] == '0'); }();
-  hipStream_t sx = use_side ? ss.s : st;
+  hipStream_t sx = side_stream_enabled() ? ss.s : st;
   HGNN_TRY(stream_after(sx, st, ss.ev[0]));   // inputs of this call are ready on the side stream too
 
   // every gradient field is written below even when there is nothing to sum over
