@@ -263,6 +263,32 @@ def test_step_is_bitwise_reproducible():
         assert np.array_equal(a.view(np.uint32), c.view(np.uint32))
 
 
+def test_side_stream_on_and_off_give_the_same_bits():
+    """Weight gradients run on the library's side stream by default; keeping them on the caller's stream must not
+    change a single bit (the sums have a fixed order either way). cfg3: bf16 pairs, i.e. the recomputing W2-gradient
+    kernel with both of its launches (whole blocks, left-over and ragged blocks)."""
+    say("side stream on/off")
+    import torch
+    from paper_2506_21788_amd import binding as B
+    P = problem_from_config("cfg3")
+    outs = []
+    before = B.set_side_stream(True)
+    try:
+        for on in (True, False, True):
+            B.set_side_stream(on)
+            hpth = gpu_hotpath(P)
+            hpth.build_graph()
+            hpth.forward()
+            hpth.backward(torch.as_tensor(P["gE"]).cuda(), torch.as_tensor(P["gF"]).cuda())
+            torch.cuda.synchronize()
+            outs.append([t.cpu().numpy().copy() for t in (hpth.energy, hpth.force, hpth.gWhead, hpth.g_emb, *hpth.gW)])
+    finally:
+        B.set_side_stream(before)
+    for other in outs[1:]:
+        for a, c in zip(outs[0], other):
+            assert np.array_equal(a.view(np.uint32), c.view(np.uint32))
+
+
 # ------------------------------------------------------------------------------------------------
 # full sizes, in the launch configuration bench.py times
 # ------------------------------------------------------------------------------------------------
