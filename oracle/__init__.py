@@ -16,6 +16,7 @@ finite differences). Nothing here can be pinned to values printed in the paper, 
 prints no intermediate value of this path: "parity unpinned" with respect to the paper's tables.
 """
 from .neighbors import radius_graph, radius_graph_rows, image_range, transpose_plan  # noqa: F401
+from .optim import adamw_step  # noqa: F401
 from .model import (  # noqa: F401
     unpack_layer,
     unpack_heads,
