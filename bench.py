@@ -192,6 +192,23 @@ def main():
     torch.cuda.synchronize()
     t_mp = (time.perf_counter() - t0) / args.steps
 
+    # AdamW update of every weight buffer (not part of `value`: the metric is the message-passing step). The step's
+    # own weights are left alone: copies are updated, with the gradients of the last step.
+    params = [(w.clone(), g) for w, g in zip([*hot.W, hot.Whead, hot.emb], [*hot.gW, hot.gWhead, hot.g_emb])]
+    moments = [(torch.zeros_like(w), torch.zeros_like(w)) for w, _ in params]
+    n_params = sum(w.numel() for w, _ in params)
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for t in range(1, 4):
+        for (w, g), (m, v) in zip(params, moments):
+            B.adamw_step(w, g, m, v, t)
+    ev0.record()
+    for t in range(4, 4 + args.steps):
+        for (w, g), (m, v) in zip(params, moments):
+            B.adamw_step(w, g, m, v, t)
+    ev1.record()
+    torch.cuda.synchronize()
+    adamw_ms = ev0.elapsed_time(ev1) / args.steps
+
     avg_s = dom_ms / max(dom_n, 1) * 1e-3
     roofline = roofline_of(dom, avg_s, N, E, H, hp["dtype"], read_traffic(args.config, dom))
     roofline["launches_per_step"] = dom_n / args.steps
@@ -206,6 +223,9 @@ def main():
         "edge_layers_per_s": E * L / t_full, "graphs_per_s": G / t_full,
         "ms_per_step_graph_prebuilt": t_mp * 1e3, "edges_per_s_graph_prebuilt": E / t_mp,
         "roofline": roofline,
+        "adamw": {"parameters": n_params, "buffers": len(params), "ms_per_update": adamw_ms,
+                  "GB_per_s": 28.0 * n_params / (adamw_ms * 1e-3) / 1e9,
+                  "note": "separate from value; 28 B per parameter (read w, g, m, v; write w, m, v)"},
         "kernel_split_note": "per kernel class, timed alone (side stream off), over 2 untimed steps",
         "kernel_split_ms_per_step": {k: round(v["ms_per_step"], 4) for k, v in
                                      sorted(split.items(), key=lambda kv: -kv[1]["ms_per_step"])},

@@ -204,6 +204,19 @@ int32_t hgnn_multihead_decode_bwd(void* stream, int32_t N, int32_t G, int32_t H,
                                   void* ws, size_t ws_bytes);
 
 /* ---------------------------------------------------------------------------------------------
+ * AdamW update of a flat float32 parameter buffer (paper, training setup: "AdamW" with learning rate 0.001;
+ * the update itself is the published algorithm, Adam with decoupled weight decay):
+ *   m <- beta1 m + (1-beta1) g;  v <- beta2 v + (1-beta2) g*g;
+ *   w <- w - lr * ( (m / (1-beta1^step)) / (sqrt(v / (1-beta2^step)) + eps) + weight_decay * w )
+ * w, m, v [n] are updated in place, g [n] is read; all device pointers, 16-byte aligned; m and v start at zero
+ * and `step` counts the updates from 1. The layer and head weight buffers of this library are flat, so one call
+ * per buffer (or one call over a buffer that holds them all) updates the model. Only enqueues work.
+ * Errors: BAD_SHAPE for n < 0, step < 1 or a beta outside [0,1); NULLPTR for a null buffer with n > 0.
+ * ------------------------------------------------------------------------------------------- */
+int32_t hgnn_adamw_step(void* stream, int64_t n, float* w, const float* g, float* m, float* v,
+                        int32_t step, double lr, double beta1, double beta2, double eps, double weight_decay);
+
+/* ---------------------------------------------------------------------------------------------
  * Instrumentation (for benchmarks; not part of the method): time classes of kernels with HIP events
  * recorded on the launch stream. _begin enables the classes whose bit is set in tag_mask and clears
  * earlier records; _end SYNCHRONISES the stream and accumulates; _read returns how many launches of

@@ -24,6 +24,7 @@ EXPORTS = [
     "hgnn_pool_by_graph_fwd", "hgnn_pool_by_graph_bwd",
     "hgnn_multihead_plan_ints", "hgnn_multihead_plan",
     "hgnn_multihead_decode_workspace_bytes", "hgnn_multihead_decode_fwd", "hgnn_multihead_decode_bwd",
+    "hgnn_adamw_step",
     "hgnn_profile_begin", "hgnn_profile_end", "hgnn_profile_num_tags", "hgnn_profile_tag_name",
     "hgnn_profile_read",
 ]
@@ -70,6 +71,8 @@ _mp_fwd = _sig("hgnn_mp_layer_fwd", vp, i32, i64, i32, i32, f32, vp, vp, vp, vp,
                vp, sz, vp, sz)
 _mp_bwd = _sig("hgnn_mp_layer_bwd", vp, i32, i64, i32, i32, f32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz,
                vp, vp, vp, vp, vp, vp, sz)
+_adamw = _sig("hgnn_adamw_step", vp, i64, vp, vp, vp, vp, i32, C.c_double, C.c_double, C.c_double, C.c_double,
+              C.c_double)
 _pool_fwd = _sig("hgnn_pool_by_graph_fwd", vp, i32, i32, i32, i32, vp, vp, vp)
 _pool_bwd = _sig("hgnn_pool_by_graph_bwd", vp, i32, i32, i32, i32, vp, vp, vp, i32)
 _plan = _sig("hgnn_multihead_plan", vp, i32, i32, i32, vp, vp, vp)
@@ -227,6 +230,11 @@ def profile_num_tags():
 
 def profile_tag_name(tag):
     return _lib.hgnn_profile_tag_name(tag).decode()
+
+
+def adamw_step(w, g, m, v, step, lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01):
+    """In-place AdamW update of the flat float32 device tensor w (moments m, v; gradient g); step counts from 1."""
+    _check(_adamw(_stream(), w.numel(), _p(w), _p(g), _p(m), _p(v), step, lr, beta1, beta2, eps, weight_decay))
 
 
 def profile_begin(tag_mask):
