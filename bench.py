@@ -128,6 +128,8 @@ def main():
     ap.add_argument("--config", default="cfg4")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--breakdown", action="store_true", help="print the per-kernel-class split to stderr")
+    ap.add_argument("--hip-graph", action="store_true",
+                    help="also time forward + backward replayed as one HIP graph (graph prebuilt)")
     ap.add_argument("--calib-copy", action="store_true", help="only run a 1 GiB copy kernel (counter calibration)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -209,6 +211,19 @@ def main():
     torch.cuda.synchronize()
     adamw_ms = ev0.elapsed_time(ev1) / args.steps
 
+    # the same forward + backward as one HIP graph (graph prebuilt), for launch-bound workloads
+    t_hg = None
+    if args.hip_graph:
+        graph = hot.capture(gE, gF)
+        for _ in range(3):
+            graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        t_hg = (time.perf_counter() - t0) / args.steps
+
     avg_s = dom_ms / max(dom_n, 1) * 1e-3
     roofline = roofline_of(dom, avg_s, N, E, H, hp["dtype"], read_traffic(args.config, dom))
     roofline["launches_per_step"] = dom_n / args.steps
@@ -222,6 +237,7 @@ def main():
                    "layers": L, "sources": hp["S"], "cutoff": hp["rc"], "alpha": hot.alpha},
         "edge_layers_per_s": E * L / t_full, "graphs_per_s": G / t_full,
         "ms_per_step_graph_prebuilt": t_mp * 1e3, "edges_per_s_graph_prebuilt": E / t_mp,
+        "ms_per_step_graph_prebuilt_hip_graph": None if t_hg is None else t_hg * 1e3,
         "roofline": roofline,
         "adamw": {"parameters": n_params, "buffers": len(params), "ms_per_update": adamw_ms,
                   "GB_per_s": 28.0 * n_params / (adamw_ms * 1e-3) / 1e9,

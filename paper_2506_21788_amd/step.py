@@ -144,3 +144,20 @@ class HotPath:
             self.build_graph()
         self.forward()
         self.backward(g_energy, g_force)
+
+    # -- HIP graph of forward + backward (graph prebuilt) ------------------------------------------
+    def capture(self, g_energy, g_force):
+        """Record forward() + backward(g_energy, g_force) into a HIP graph and return it (replay() launches it).
+
+        Both only enqueue kernels and event fork/joins of the library's side stream, all of which a stream capture
+        records. Everything that allocates or sets kernel attributes happens on first use, so one eager step runs
+        first. The graph reads and writes this object's buffers and the two gradient tensors given here: refill
+        those in place before a replay. The radius graph is not part of it (its count call synchronises)."""
+        self.forward()
+        self.backward(g_energy, g_force)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            self.forward()
+            self.backward(g_energy, g_force)
+        return graph

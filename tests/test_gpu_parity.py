@@ -289,6 +289,39 @@ def test_side_stream_on_and_off_give_the_same_bits():
             assert np.array_equal(a.view(np.uint32), c.view(np.uint32))
 
 
+@pytest.mark.parametrize("name", ["cfg1", "cfg3"])
+def test_hip_graph_replays_match_eager_bitwise(name):
+    """forward + backward recorded into a HIP graph: every replay, with eager work and synchronisations between
+    the replays, gives the bits of the eager step."""
+    say(f"hip graph {name}")
+    import torch
+    P = problem_from_config(name)
+    gE, gF = torch.as_tensor(P["gE"]).cuda(), torch.as_tensor(P["gF"]).cuda()
+    hpth = gpu_hotpath(P)
+    hpth.build_graph()
+
+    def outputs():
+        torch.cuda.synchronize()
+        return [t.cpu().numpy().copy() for t in (hpth.energy, hpth.force, hpth.gWhead, hpth.g_emb, hpth.g_h0, *hpth.gW)]
+
+    hpth.forward()
+    hpth.backward(gE, gF)
+    want = outputs()
+    graph = hpth.capture(gE, gF)
+    for rep in range(3):
+        for t in (hpth.energy, hpth.force, hpth.gWhead, hpth.g_emb, *hpth.gW):
+            t.fill_(float("nan"))          # eager work between replays; also proves the replay rewrites everything
+        torch.cuda.synchronize()
+        graph.replay()
+        got = outputs()
+        for a, c in zip(want, got):
+            assert np.array_equal(a.view(np.uint32), c.view(np.uint32)), rep
+        hpth.forward()                       # an eager step in between
+        hpth.backward(gE, gF)
+        for a, c in zip(want, outputs()):
+            assert np.array_equal(a.view(np.uint32), c.view(np.uint32)), rep
+
+
 # ------------------------------------------------------------------------------------------------
 # full sizes, in the launch configuration bench.py times
 # ------------------------------------------------------------------------------------------------
