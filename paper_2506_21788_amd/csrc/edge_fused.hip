@@ -5,6 +5,8 @@
 //   k_edge_bwd    g_z2 from z2 / g_M / g_v -> x W2^T -> recompute z1 -> g_z1, plus the three per-column
 //                 sums that are bias / vector gradients
 //   k_wgrad_frag  g_W2 = a1^T g_z2 streamed straight from memory into matrix-core operands
+//   k_wgrad_frag_rc  the same with a1 recomputed from the projected node features (bf16 pairs), so that the
+//                 forward kernel need not store it
 //   k_segsum_vm   segmented sums of g_z1 per destination and (through the transpose plan) per source
 //
 // All element-wise work uses the accumulator mapping (lane <-> column, register <-> edge), so what one
@@ -34,26 +36,6 @@ struct ECfg {
 };
 
 __device__ __forceinline__ float bf_bits_to_f(unsigned short b) { return __uint_as_float(((unsigned)b) << 16); }
-
-// the 4 consecutive per-edge scalars e4..e4+3 (e4 is a multiple of 4); zeros beyond E
-__device__ __forceinline__ void load4(const int32_t* __restrict__ p, int64_t e4, int64_t E, int* o) {
-  if (e4 + 3 < E) {
-    const int4 t = *reinterpret_cast<const int4*>(p + e4);
-    o[0] = t.x; o[1] = t.y; o[2] = t.z; o[3] = t.w;
-  } else {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) o[i] = (e4 + i < E) ? p[e4 + i] : 0;
-  }
-}
-__device__ __forceinline__ void load4(const float* __restrict__ p, int64_t e4, int64_t E, float* o) {
-  if (e4 + 3 < E) {
-    const float4 t = *reinterpret_cast<const float4*>(p + e4);
-    o[0] = t.x; o[1] = t.y; o[2] = t.z; o[3] = t.w;
-  } else {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) o[i] = (e4 + i < E) ? p[e4 + i] : 0.f;
-  }
-}
 
 // Streaming accesses are written as (uniform 64-bit base) + (32-bit per-lane byte offset): the base lives in scalar
 // registers, the lane part is one register shared by every access, and constant strides fold into the instruction.
