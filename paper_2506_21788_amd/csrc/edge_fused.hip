@@ -1222,15 +1222,18 @@ __global__ void __launch_bounds__(256) k_wgrad_frag_rc(WgradRcArgs p) {
       }
 }
 
-constexpr int WGRAD_FRAG_MAX_GRID = 512;
-size_t wgrad_frag_partial_floats(int H) { return (size_t)WGRAD_FRAG_MAX_GRID * H * H; }
+// most workgroups (= partial H x H results) of one launch: the partial buffer holds 32 Mi floats at every H
+constexpr int WGRAD_FRAG_MAX_GRID = 512;                        // at H = 256
+static int wgrad_frag_max_grid(int H) { return WGRAD_FRAG_MAX_GRID * (256 / H) * (256 / H); }
+size_t wgrad_frag_partial_floats(int H) { return (size_t)wgrad_frag_max_grid(H) * H * H; }
 
 template <int H, bool BF16>
 static int32_t launch_wgrad_frag_t(hipStream_t st, int64_t E, const void* a1_pk, const void* gz2_pk, float* partial,
                                    float* gW2) {
   const int64_t nblk32 = (E + 31) / 32;
-  int64_t grid = (int64_t)num_cus() * (H == 256 ? 1 : 2);
-  if (grid > WGRAD_FRAG_MAX_GRID) grid = WGRAD_FRAG_MAX_GRID;
+  // one workgroup per CU holds the whole accumulator at H = 256; narrower ones leave room for four (eight)
+  int64_t grid = (int64_t)num_cus() * (H == 256 ? 1 : (H == 128 ? 4 : 8));
+  if (grid > wgrad_frag_max_grid(H)) grid = wgrad_frag_max_grid(H);
   if (grid > nblk32) grid = nblk32;
   if (grid < 1) grid = 1;
   {
