@@ -338,6 +338,49 @@ __device__ __forceinline__ void edge_fwd_tile(
   // byte offset of this lane's first column inside a row: word wc*32 + x of bf16 pairs, else column wc*CB*32 + x
   const unsigned colb = (unsigned)((PAIRS ? wc * 32 : wc * C::CB * 32) + x) * 4u;
   // ---- produce a1 for this wavefront's blocks: memory (operand-packed) and LDS (row-major)
+  if constexpr (PAIRS && FULL) {
+    // Groups of 8 edges, software-pipelined: the gathers of the next group are in flight while this one is turned
+    // into a1 (the accumulator registers are free in this phase and hold the second set of gathered words; a third
+    // set would spill).
+    using PQP = PQPitch<H, true>;
+    constexpr int NG = C::RB * 2;
+    constexpr int NS = 2;
+    unsigned wp[NS][8], wq[NS][8];
+    float dd[NS][8];
+    auto issue = [&](int gi, unsigned (&wpo)[8], unsigned (&wqo)[8], float (&ddo)[8]) {
+      const int rblk = wr * C::RB + (gi >> 1), vh = gi & 1;
+      int di[8], ci[8];
+      lds_rows8(s, rblk, vh, g, di);
+      lds_rows8(s + C::TM, rblk, vh, g, ci);
+      lds_rows8(s + 2 * C::TM, rblk, vh, g, ddo);
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        wpo[u] = ldg_u32(p.PQ, (unsigned)di[u] * PQP::ROW + colb);
+        wqo[u] = ldg_u32(p.PQ, (unsigned)ci[u] * PQP::ROW + colb + PQP::QOFF);
+      }
+    };
+#pragma unroll
+    for (int gi = 0; gi < NS - 1; ++gi) issue(gi, wp[gi], wq[gi], dd[gi]);
+#pragma unroll
+    for (int gi = 0; gi < NG; ++gi) {
+      if (gi + NS - 1 < NG) issue(gi + NS - 1, wp[(gi + NS - 1) % NS], wq[(gi + NS - 1) % NS], dd[(gi + NS - 1) % NS]);
+      const int sl = gi % NS;
+      const int rblk = wr * C::RB + (gi >> 1), vh = gi & 1;
+      const int eb = tile * (C::TM / 32) + rblk;
+#pragma unroll
+      for (int j = 0; j < C::CB; ++j) {
+        const int cblk = wc * C::CB + j;
+        float vals[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const float zp = j == 0 ? __uint_as_float(wp[sl][u] << 16) : __uint_as_float(wp[sl][u] & 0xffff0000u);
+          const float zq = j == 0 ? __uint_as_float(wq[sl][u] << 16) : __uint_as_float(wq[sl][u] & 0xffff0000u);
+          vals[u] = silu_f(zp + zq + dd[sl][u] * w1d[j]);
+        }
+        emit_half<BF16, C::STRIDE>(smem, rblk * 32, g, cblk * 32 + x, vals, vh, p.a1_pk, (size_t)eb * C::NCB + cblk, lane);
+      }
+    }
+  } else
 #pragma unroll
   for (int i = 0; i < C::RB; ++i) {
     const int rblk = wr * C::RB + i;
