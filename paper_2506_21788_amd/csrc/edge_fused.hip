@@ -751,6 +751,52 @@ __device__ __forceinline__ void edge_bwd_tile(const EdgeBwdArgs& p, unsigned cha
   // byte offset of this lane's first column inside a row: word wc*32 + x of bf16 pairs, else column wc*CB*32 + x
   const unsigned colb = (unsigned)((PAIRS ? wc * 32 : wc * C::CB * 32) + x) * 4u;
   // ---- g_z2 = (alpha*g_M[dst] + c*wx) * silu'(z2): operand-packed to memory, row-major to LDS
+  if constexpr (PAIRS && FULL) {
+    // groups of 8 edges, software-pipelined: the loads of the next group are in flight while this one is processed
+    // (the accumulator registers are free in this phase; the same in the last phase, where they are not, spills)
+    constexpr int NG = C::RB * 2;
+    unsigned zw[2][8], gw[2][8];
+    float cc[2][8];
+    auto issue = [&](int gi, unsigned (&zo)[8], unsigned (&go)[8], float (&co)[8]) {
+      const int rblk = wr * C::RB + (gi >> 1), vh = gi & 1;
+      const int eb = tile * (C::TM / 32) + rblk;
+      int di[8];
+      lds_rows8(s, rblk, vh, g, di);
+      lds_rows8(s + 3 * C::TM, rblk, vh, g, co);
+      const char* zp = uoff(p.z2_vm, (((size_t)eb * (C::NCB / 2) + wc) * 16 + 8 * vh) * 256);
+#pragma unroll
+      for (int u = 0; u < 8; ++u) zo[u] = ldg_nt<unsigned>(zp, lane * 4u + u * 256u);
+#pragma unroll
+      for (int u = 0; u < 8; ++u) go[u] = ldg_u32(p.gM, (unsigned)di[u] * GM_ROW + colb);
+    };
+    issue(0, zw[0], gw[0], cc[0]);
+#pragma unroll
+    for (int gi = 0; gi < NG; ++gi) {
+      if (gi + 1 < NG) issue(gi + 1, zw[(gi + 1) & 1], gw[(gi + 1) & 1], cc[(gi + 1) & 1]);
+      const int sl = gi & 1;
+      const int rblk = wr * C::RB + (gi >> 1), vh = gi & 1;
+      const int eb = tile * (C::TM / 32) + rblk;
+#pragma unroll
+      for (int j = 0; j < C::CB; ++j) {
+        const int cblk = wc * C::CB + j;
+        float vals[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const float zz = j == 0 ? __uint_as_float(zw[sl][u] << 16) : __uint_as_float(zw[sl][u] & 0xffff0000u);
+          const float gmv = j == 0 ? __uint_as_float(gw[sl][u] << 16) : __uint_as_float(gw[sl][u] & 0xffff0000u);
+          float m, dm;
+          silu_both(zz, m, dm);
+          const float gz = fmaf(cc[sl][u], wxn[j], gmv) * dm;   // the pair form holds alpha * g_M
+          vals[u] = gz;
+          sb2[j] += gz;
+          swx[j] += cc[sl][u] * m;
+        }
+        emit_half<BF16, C::STRIDE>(smem, rblk * 32, g, cblk * 32 + x, vals, vh, p.gz2_pk, (size_t)eb * C::NCB + cblk, lane);
+      }
+#pragma unroll
+      for (int j = 0; j < C::CB; ++j) asm volatile("" : "+v"(sb2[j]), "+v"(swx[j]));
+    }
+  } else
 #pragma unroll
   for (int i = 0; i < C::RB; ++i) {
     const int rblk = wr * C::RB + i;
