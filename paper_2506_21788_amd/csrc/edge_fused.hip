@@ -866,6 +866,47 @@ __device__ __forceinline__ void edge_bwd_tile(const EdgeBwdArgs& p, unsigned cha
   s_next[tid] = nxt;
   __syncthreads();
   // ---- g_z1 = g_a1 * silu'(z1), z1 recomputed from the projected node features
+  if constexpr (PAIRS && FULL) {
+    // the same pipelining; d2 is read from LDS when it is used so that only the gathered words live twice
+    using PQP = PQPitch<H, true>;
+    constexpr int NG = C::RB * 2;
+    unsigned wp[2][8], wq[2][8];
+    auto issue = [&](int gi, unsigned (&wpo)[8], unsigned (&wqo)[8]) {
+      const int rblk = wr * C::RB + (gi >> 1), vh = gi & 1;
+      int di[8], ci[8];
+      lds_rows8(s, rblk, vh, g, di);
+      lds_rows8(s + C::TM, rblk, vh, g, ci);
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        wpo[u] = ldg_u32(p.PQ, (unsigned)di[u] * PQP::ROW + colb);
+        wqo[u] = ldg_u32(p.PQ, (unsigned)ci[u] * PQP::ROW + colb + PQP::QOFF);
+      }
+    };
+    issue(0, wp[0], wq[0]);
+#pragma unroll
+    for (int gi = 0; gi < NG; ++gi) {
+      if (gi + 1 < NG) issue(gi + 1, wp[(gi + 1) & 1], wq[(gi + 1) & 1]);
+      const int sl = gi & 1;
+      const int i = gi >> 1, vh = gi & 1;
+      const int rblk = wr * C::RB + i;
+      const int eb = tile * (C::TM / 32) + rblk;
+      float dd[8];
+      lds_rows8(s + 2 * C::TM, rblk, vh, g, dd);
+      char* o = uoff(p.gz1_vm, (((size_t)eb * (C::NCB / 2) + wc) * 16 + 8 * vh) * 256);
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const float z0 = __uint_as_float(wp[sl][u] << 16) + __uint_as_float(wq[sl][u] << 16) + dd[u] * w1d[0];
+        const float z1 = __uint_as_float(wp[sl][u] & 0xffff0000u) + __uint_as_float(wq[sl][u] & 0xffff0000u) + dd[u] * w1d[1];
+        const float g0 = acc[i][0][8 * vh + u] * dsilu_f(z0);
+        const float g1 = acc[i][1][8 * vh + u] * dsilu_f(z1);
+        sw1[0] += dd[u] * g0;
+        sw1[1] += dd[u] * g1;
+        stg_nt<unsigned>(o, lane * 4u + u * 256u, pack_bf16x2(g0, g1));
+      }
+#pragma unroll
+      for (int j = 0; j < C::CB; ++j) asm volatile("" : "+v"(sw1[j]));
+    }
+  } else
 #pragma unroll
   for (int i = 0; i < C::RB; ++i) {
     const int rblk = wr * C::RB + i;
