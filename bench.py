@@ -91,6 +91,24 @@ def calib_copy():
     print(json.dumps({"calib_copy_bytes_read": n * 4, "calib_copy_bytes_written": n * 4, "copies": 5}))
 
 
+def calib_mfma():
+    """What the matrix pipes sustain on register-only work (context for the published peaks)."""
+    import torch
+    from paper_2506_21788_amd import binding as B
+    sink = torch.zeros(1, dtype=torch.float32, device="cuda")
+    out = {}
+    for name, dt in (("bf16", B.BF16), ("f32", B.F32)):
+        B.mfma_probe(dt, 2048, 256, sink)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        flops = B.mfma_probe(dt, 2048, 8192, sink)
+        e1.record()
+        torch.cuda.synchronize()
+        out[name] = {"TFLOP_per_s": flops / (e0.elapsed_time(e1) * 1e-3) / 1e12, "published_peak": PEAK_TFLOPS[name]}
+    print(json.dumps({"calib_mfma": out}))
+
+
 def cpu_baseline(P, target_edges=150000):
     """The oracle, as it stands, on a bounded sample (the first graphs of the same batch)."""
     import numpy as np
@@ -131,6 +149,7 @@ def main():
     ap.add_argument("--hip-graph", action="store_true",
                     help="also time forward + backward replayed as one HIP graph (graph prebuilt)")
     ap.add_argument("--calib-copy", action="store_true", help="only run a 1 GiB copy kernel (counter calibration)")
+    ap.add_argument("--calib-mfma", action="store_true", help="only run the matrix-core rate probe")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; no figure at several GPUs exists (--gpus 1 only)",
@@ -139,6 +158,9 @@ def main():
 
     if args.calib_copy:
         calib_copy()
+        return
+    if args.calib_mfma:
+        calib_mfma()
         return
     import torch
     from parity_util import gpu_hotpath, problem_from_config

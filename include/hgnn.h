@@ -229,6 +229,12 @@ int32_t hgnn_profile_num_tags(void);
 const char* hgnn_profile_tag_name(int32_t tag);
 int32_t hgnn_profile_read(int32_t tag, int64_t* launches_host, double* total_ms_host);
 
+/* Matrix-core rate probe (instrumentation): launches `workgroups` x 4 wavefronts that each issue 4 * iters
+ * register-only 32x32 matrix-core instructions (dtype HGNN_BF16: 32x32x16 bf16; HGNN_F32: 32x32x2 fp32) and
+ * returns the number of floating-point operations that launch performs (0 on a bad argument or launch failure).
+ * The caller times it; `sink` is one device float that is never written in practice. Only enqueues work. */
+int64_t hgnn_mfma_probe(void* stream, int32_t dtype, int32_t workgroups, int32_t iters, float* sink);
+
 #ifdef __cplusplus
 }
 #endif

@@ -99,3 +99,50 @@ extern "C" int32_t hgnn_profile_read(int32_t tag, int64_t* launches_host, double
   *total_ms_host = g_ms[tag];
   return HGNN_OK;
 }
+
+// ---------------------------------------------------------------------------------------------
+// Matrix-core rate probe (instrumentation): every wavefront runs `iters` rounds of four independent
+// 32x32 matrix-core instructions on registers only, so the kernel measures what the matrix pipes sustain
+// (to set the published peak beside a measured one). Returns the number of floating-point operations issued.
+// ---------------------------------------------------------------------------------------------
+namespace hgnn {
+typedef float probe_f32x16 __attribute__((ext_vector_type(16)));
+typedef __bf16 probe_bf16x8 __attribute__((ext_vector_type(8)));
+
+template <bool BF16>
+__global__ void __launch_bounds__(256) k_mfma_probe(int iters, float* sink) {
+  probe_f32x16 acc[4];
+#pragma unroll
+  for (int k = 0; k < 4; ++k)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[k][v] = 0.f;
+  const float seed = 1.0f + (float)(threadIdx.x & 7) * 0.125f;
+  probe_bf16x8 a, b;
+#pragma unroll
+  for (int t = 0; t < 8; ++t) { a[t] = (__bf16)seed; b[t] = (__bf16)(0.5f * seed); }
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      if constexpr (BF16) acc[k] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[k], 0, 0, 0);
+      else acc[k] = __builtin_amdgcn_mfma_f32_32x32x2f32(seed, 0.5f * seed, acc[k], 0, 0, 0);
+    }
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int k = 0; k < 4; ++k)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) s += acc[k][v];
+  if (s == 12345.678f) sink[0] = s;   // keeps the loop alive; never true in practice
+}
+}  // namespace hgnn
+
+extern "C" int64_t hgnn_mfma_probe(void* stream, int32_t dtype, int32_t workgroups, int32_t iters, float* sink) {
+  if (workgroups <= 0 || iters <= 0 || !sink) return 0;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const bool bf16 = dtype == 1;
+  if (bf16) hgnn::k_mfma_probe<true><<<dim3((unsigned)workgroups), 256, 0, st>>>(iters, sink);
+  else hgnn::k_mfma_probe<false><<<dim3((unsigned)workgroups), 256, 0, st>>>(iters, sink);
+  if (hipGetLastError() != hipSuccess) return 0;
+  const int64_t per_instr = bf16 ? 2LL * 32 * 32 * 16 : 2LL * 32 * 32 * 2;
+  return (int64_t)workgroups * 4 /*wavefronts*/ * iters * 4 * per_instr;
+}
