@@ -1,0 +1,75 @@
+"""One message-passing layer, forward and reverse, on synthetic destination-sorted edge lists of chosen sizes:
+edge counts around the tile / block / launch boundaries of the edge kernels (needs a GPU)."""
+import numpy as np
+import pytest
+
+import oracle
+from hgnn_inputs.weights import init_layer_weights
+from parity_util import TOL, relerr
+
+pytestmark = pytest.mark.gpu
+
+
+def _edges(rng, N, E):
+    """E directed edges, sorted by destination, random sources and geometry; some atoms have no edge."""
+    dst = np.sort(rng.integers(0, N, size=E)).astype(np.int32)
+    col = rng.integers(0, N, size=E).astype(np.int32)
+    rvec = (rng.standard_normal((E, 3)) * 1.5).astype(np.float32)
+    d2 = (rvec.astype(np.float64) ** 2).sum(1).astype(np.float32)
+    row_ptr = np.zeros(N + 1, np.int32)
+    row_ptr[1:] = np.cumsum(np.bincount(dst, minlength=N))
+    return row_ptr, dst, col, d2, rvec
+
+
+def _run_layer(N, E, H, dtype, seed):
+    import torch
+    from paper_2506_21788_amd import binding as B
+    rng = np.random.default_rng(seed)
+    row_ptr, dst, col, d2, rvec = _edges(rng, N, E)
+    colT_ptr, permT = oracle.transpose_plan(col, N)
+    W = init_layer_weights(rng, H).astype(np.float32)
+    h = rng.standard_normal((N, H)).astype(np.float32)
+    v = (rng.standard_normal((N, 3)) * 0.3).astype(np.float32)
+    gh = rng.standard_normal((N, H)).astype(np.float32)
+    gv = rng.standard_normal((N, 3)).astype(np.float32)
+    alpha = 1.0 / max(1.0, E / N)
+    dt = {"f32": B.F32, "bf16": B.BF16}[dtype]
+    dev = lambda a: torch.as_tensor(a).cuda()
+    ws_b, saved_b = B.mp_layer_workspace_bytes(N, E, H, dt)
+    ws = torch.empty(ws_b, dtype=torch.uint8, device="cuda")
+    saved = torch.empty(saved_b, dtype=torch.uint8, device="cuda")
+    t = dict(row_ptr=dev(row_ptr), dst=dev(dst), col=dev(col), d2=dev(d2), rvec=dev(rvec), colT=dev(colT_ptr),
+             permT=dev(permT.astype(np.int32)), h=dev(h), v=dev(v), W=dev(W), gh=dev(gh), gv=dev(gv))
+    h_out, v_out = torch.empty_like(t["h"]), torch.empty_like(t["v"])
+    g_h, g_v, gW = torch.empty_like(t["h"]), torch.empty_like(t["v"]), torch.empty_like(t["W"])
+    B.mp_layer_fwd(N, E, H, dt, alpha, t["row_ptr"], t["dst"], t["col"], t["d2"], t["rvec"], t["h"], t["v"], t["W"],
+                   h_out, v_out, saved, ws)
+    B.mp_layer_bwd(N, E, H, dt, alpha, t["row_ptr"], t["dst"], t["col"], t["d2"], t["rvec"], t["colT"], t["permT"],
+                   t["h"], t["W"], saved, t["gh"], t["gv"], g_h, g_v, gW, ws)
+    torch.cuda.synchronize()
+    ho, vo, cache = oracle.mp_layer_fwd(h, v, dst, col, d2, rvec, W.astype(np.float64), alpha)
+    gho, gvo, gWo = oracle.mp_layer_bwd(cache, gh, gv)
+    tol = TOL[dtype]
+    errs = dict(h=relerr(h_out.cpu().numpy(), ho), v=relerr(v_out.cpu().numpy(), vo),
+                g_h=relerr(g_h.cpu().numpy(), gho), g_v=relerr(g_v.cpu().numpy(), gvo))
+    got = oracle.unpack_layer(gW.cpu().numpy(), H)
+    for k, want in gWo.items():
+        errs["gW." + k] = relerr(got[k], want)
+    print(f"layer N={N} E={E} H={H} {dtype}", {k: f"{e:.1e}" for k, e in errs.items()}, flush=True)
+    for k, e in errs.items():
+        assert e <= (tol["fwd"] if k in ("h", "v") else tol["grad"]), (k, e)
+
+
+# With bf16 operands at H = 256 the W2 gradient has a branch-free launch over an even number of whole 32-edge blocks
+# per workgroup (needs at least 2 x 256 blocks = 16384 edges) and a checking launch for the rest; the fused edge
+# kernels work on 64-edge tiles with a masked last tile.
+@pytest.mark.parametrize("E", [0, 1, 31, 32, 33, 63, 64, 65, 16383, 16384, 16385, 16384 + 32, 16384 + 63,
+                               2 * 16384 + 97, 3 * 16384 - 1])
+def test_layer_bf16_pairs_edge_counts(E):
+    _run_layer(N=700, E=E, H=256, dtype="bf16", seed=E + 1)
+
+
+@pytest.mark.parametrize("H,dtype,E", [(64, "f32", 1000), (64, "bf16", 4097), (128, "f32", 8191), (128, "bf16", 8193),
+                                       (256, "f32", 4095)])
+def test_layer_other_modes_edge_counts(H, dtype, E):
+    _run_layer(N=300, E=E, H=H, dtype=dtype, seed=E)
