@@ -81,8 +81,13 @@ struct WgradArgs {
   float* dest[4] = {nullptr, nullptr, nullptr, nullptr};  // block ia*nB+ib -> H*H floats, row-major
   long grp_dest_stride = 0;
   float* partial = nullptr;  // scratch, wgrad_partial_floats()
+  // optional: column sums of the B operands (the bias gradients that go with these weight gradients), taken from
+  // the tiles the kernel stages anyway: colsum_dest[ib] (H floats, may be null) = sum over rows of B[ib]
+  float* colsum_dest[2] = {nullptr, nullptr};
+  float* colsum_partial = nullptr;   // scratch, wgrad_colsum_partial_floats()
   int tag = PT_WGRAD_NODE;
 };
+size_t wgrad_colsum_partial_floats(int H, int64_t M);
 int wgrad_splits(int64_t M);
 size_t wgrad_partial_floats(int H, int64_t M, int nblocks, int S);
 int32_t launch_wgrad(hipStream_t st, int H, bool bf16, const WgradArgs& a);

@@ -390,7 +390,7 @@ struct ReduceArgs {
 __global__ void __launch_bounds__(256) k_reduce_partials(ReduceArgs a) {
   const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
   const int blk = blockIdx.y, grp = blockIdx.z;
-  if (i >= a.blk_elems) return;
+  if (i >= a.blk_elems || !a.dest[blk]) return;
   const float* p = a.partial + ((long)grp * a.nsplit * a.nblk + blk) * a.blk_elems + i;
   const long step = (long)a.nblk * a.blk_elems;
   // ascending order of the partials is kept; sixteen loads are in flight at a time
@@ -418,6 +418,7 @@ __global__ void __launch_bounds__(256) k_reduce_partials_tall(ReduceArgs a) {
   const int k0 = ph * per;
   const int k1 = k0 + per < a.nsplit ? k0 + per : a.nsplit;
   float s = 0.f;
+  if (!a.dest[blk]) return;   // uniform over the block
   if (i < a.blk_elems) {
     const float* p = a.partial + ((long)grp * a.nsplit * a.nblk + blk) * a.blk_elems + i;
     const long step = (long)a.nblk * a.blk_elems;
@@ -514,6 +515,11 @@ __global__ void __launch_bounds__(256) k_wgrad(WgradArgs p, int nsplit, int rows
       vb[u] = *reinterpret_cast<const float4*>(B + gr * ldb + tb * C::OT + q * 4);
     }
   };
+  // column sums of this workgroup's B tile ride along where they are asked for (one workgroup per B tile: the
+  // one of the first A block and the first A tile); a thread's chunk column is the same at every step
+  const bool do_cs = p.colsum_partial != nullptr && ia == 0 && ta == 0;
+  static_assert(256 % CH == 0, "a thread keeps its chunk column over the steps");
+  float4 cs = make_float4(0.f, 0.f, 0.f, 0.f);
   if (rbeg < rend) fetch(rbeg);
   for (long r0 = rbeg; r0 < rend; r0 += WG_RC) {
     __syncthreads();
@@ -524,6 +530,7 @@ __global__ void __launch_bounds__(256) k_wgrad(WgradArgs p, int nsplit, int rows
       float4 a = va[u], b = vb[u];
       if (p.a_silu) { a.x = silu_f(a.x); a.y = silu_f(a.y); a.z = silu_f(a.z); a.w = silu_f(a.w); }
       if (r0 + r >= rend) { a = make_float4(0.f, 0.f, 0.f, 0.f); b = a; }
+      cs.x += b.x; cs.y += b.y; cs.z += b.z; cs.w += b.w;
       *reinterpret_cast<float4*>(&sA[r * C::STRIDE + q * 4]) = a;
       *reinterpret_cast<float4*>(&sB[r * C::STRIDE + q * 4]) = b;
     }
@@ -574,6 +581,20 @@ __global__ void __launch_bounds__(256) k_wgrad(WgradArgs p, int nsplit, int rows
       }
     }
   }
+  if (do_cs) {   // uniform over the workgroup: row phases are added in order through LDS
+    __syncthreads();
+    float4* sh = reinterpret_cast<float4*>(sA);
+    sh[tid] = cs;
+    __syncthreads();
+    if (tid < CH) {
+      float4 s = sh[tid];
+      for (int k = 1; k < 256 / CH; ++k) {
+        const float4 t = sh[k * CH + tid];
+        s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
+      }
+      *reinterpret_cast<float4*>(p.colsum_partial + (((long)grp * nsplit + split) * p.nB + ib) * H + tb * C::OT + tid * 4) = s;
+    }
+  }
   const int nblk = p.nA * p.nB;
   float* out = p.partial + (((long)grp * nsplit + split) * nblk + blkid) * (long)(H * H);
 #pragma unroll
@@ -595,6 +616,8 @@ int wgrad_splits(int64_t M) {
   return (int)s;
 }
 
+size_t wgrad_colsum_partial_floats(int H, int64_t M) { return (size_t)wgrad_splits(M) * 2 * H; }
+
 size_t wgrad_partial_floats(int H, int64_t M, int nblocks, int S) {
   return (size_t)wgrad_splits(M) * nblocks * S * H * H;
 }
@@ -615,12 +638,18 @@ static int32_t launch_wgrad_t(hipStream_t st, const WgradArgs& a) {
   ProfScope ps(a.tag, st);
   k_wgrad<H, BF16><<<dim3(nsplit, nblk * C::TILES * C::TILES, groups), 256, 0, st>>>(a, nsplit, (int)rps);
   HGNN_LAUNCH_CHECK("k_wgrad");
-  return launch_reduce_partials(st, a.partial, nsplit, nblk, (long)H * H, a.dest, groups, a.grp_dest_stride);
+  HGNN_TRY(launch_reduce_partials(st, a.partial, nsplit, nblk, (long)H * H, a.dest, groups, a.grp_dest_stride));
+  if (a.colsum_partial) {
+    float* cd[4] = {a.colsum_dest[0], a.colsum_dest[1], nullptr, nullptr};
+    HGNN_TRY(launch_reduce_partials(st, a.colsum_partial, nsplit, a.nB, H, cd, 1, 0));
+  }
+  return HGNN_OK;
 }
 
 int32_t launch_wgrad(hipStream_t st, int H, bool bf16, const WgradArgs& a) {
   HGNN_REQUIRE(a.nA >= 1 && a.nB >= 1 && a.nA * a.nB <= 4, HGNN_ERR_BAD_SHAPE, "wgrad: bad block counts");
   HGNN_REQUIRE(a.A[0] && a.B[0] && a.partial && a.dest[0], HGNN_ERR_NULLPTR, "wgrad: null operand");
+  HGNN_REQUIRE(!a.colsum_partial || !a.grp_ptr, HGNN_ERR_BAD_SHAPE, "wgrad: column sums are not available per group");
   switch (H) {
     case 64: return bf16 ? launch_wgrad_t<64, true>(st, a) : launch_wgrad_t<64, false>(st, a);
     case 128: return bf16 ? launch_wgrad_t<128, true>(st, a) : launch_wgrad_t<128, false>(st, a);

@@ -65,6 +65,7 @@ struct LayerWs {
   float* g_PQ;     // [N,2H]
   float* partial;  // split-K / column-sum partials of the main stream
   float* partial2; // the same for the work that runs on the side stream
+  float* cs_partial;  // column-sum partials of the node weight-gradient kernel (side stream)
   size_t bytes;
 };
 
@@ -84,6 +85,7 @@ static LayerWs carve_ws(void* p, int N, int64_t E, int H, bool bf16) {
   for (size_t x : cands) pf = x > pf ? x : pf;
   w.partial = c.take<float>(pf);
   w.partial2 = c.take<float>(pf);
+  w.cs_partial = c.take<float>(wgrad_colsum_partial_floats(H, N));
   w.bytes = c.used();
   return w;
 }
@@ -272,17 +274,15 @@ extern "C" int32_t hgnn_mp_layer_bwd(void* stream, int32_t N, int64_t E, int32_t
   HGNN_TRY(stream_after(sx, st, ss.ev[0]));   // inputs of this call are ready on the side stream too
 
   // every gradient field is written below even when there is nothing to sum over
-  {  // side: gW4 = silu(z3)^T g_h' ; gb4   (inputs only)
+  {  // side: gW4 = silu(z3)^T g_h' ; gb4 = column sums of g_h' (taken by the same kernel)   (inputs only)
     WgradArgs a;
     a.A[0] = s.z3; a.lda[0] = H; a.a_silu = 1;
     a.B[0] = g_h_out; a.ldb[0] = H;
     a.M = N;
     a.dest[0] = gW + o.W4;
     a.partial = w.partial2;
+    a.colsum_dest[0] = gW + o.b4; a.colsum_partial = w.cs_partial;
     HGNN_TRY(launch_wgrad(sx, H, bf16, a));
-    ColsumArgs c;
-    c.X = g_h_out; c.ldx = H; c.M = N; c.dest = gW + o.b4; c.partial = w.partial2;
-    HGNN_TRY(launch_colsum(sx, H, c));
   }
   {  // g_z3 = (g_h' W4^T) * silu'(z3)
     GemmArgs g;
@@ -301,10 +301,8 @@ extern "C" int32_t hgnn_mp_layer_bwd(void* stream, int32_t N, int64_t E, int32_t
     a.M = N;
     a.dest[0] = gW + o.W3; a.dest[1] = gW + o.W3 + HH;
     a.partial = w.partial2;
+    a.colsum_dest[0] = gW + o.b3; a.colsum_partial = w.cs_partial;
     HGNN_TRY(launch_wgrad(sx, H, bf16, a));
-    ColsumArgs c;
-    c.X = w.g_z3; c.ldx = H; c.M = N; c.dest = gW + o.b3; c.partial = w.partial2;
-    HGNN_TRY(launch_colsum(sx, H, c));
   }
   {  // [g_h(a) | g_M] = g_z3 W3^T
     GemmArgs g;
@@ -346,16 +344,14 @@ extern "C" int32_t hgnn_mp_layer_bwd(void* stream, int32_t N, int64_t E, int32_t
   HGNN_TRY(launch_segsum_vm(st, H, bf16, N, row_ptr, nullptr, w.gz1_vm, w.g_PQ, 2 * H, PT_SEGSUM_DST));     // g_P
   HGNN_TRY(launch_segsum_vm(st, H, bf16, N, colT_ptr, permT, w.gz1_vm, w.g_PQ + H, 2 * H, PT_SEGSUM_SRC));  // g_Q
   HGNN_TRY(stream_after(sx, st, ss.ev[3]));
-  {  // side: gb1 = sum_i g_P_i ; gW1a = h^T g_P ; gW1b = h^T g_Q
-    ColsumArgs c2;
-    c2.X = w.g_PQ; c2.ldx = 2 * H; c2.M = N; c2.dest = gW + o.b1; c2.partial = w.partial2;
-    HGNN_TRY(launch_colsum(sx, H, c2));
+  {  // side: gW1a = h^T g_P ; gW1b = h^T g_Q ; gb1 = sum_i g_P_i (column sums of the first B operand)
     WgradArgs a;
     a.A[0] = h_in; a.lda[0] = H;
     a.B[0] = w.g_PQ; a.ldb[0] = 2 * H; a.B[1] = w.g_PQ + H; a.ldb[1] = 2 * H; a.nB = 2;
     a.M = N;
     a.dest[0] = gW + o.W1; a.dest[1] = gW + o.W1 + HH;
     a.partial = w.partial2;
+    a.colsum_dest[0] = gW + o.b1; a.colsum_partial = w.cs_partial;
     HGNN_TRY(launch_wgrad(sx, H, bf16, a));
   }
   {  // g_h = g_h' + g_h(a) + g_P W1a^T + g_Q W1b^T
