@@ -326,12 +326,34 @@ __device__ __forceinline__ unsigned rows8_mask(int eb, int vh, int g, int E) {
 // ---------------------------------------------------------------------------------------------
 // forward
 // ---------------------------------------------------------------------------------------------
+// Gathers of one group of 8 edges (bf16 pairs): the pair words of P[dst] and Q[col] and d2, from the tile's
+// scalars in LDS. Group gi of a wavefront: row block gi >> 1, register half gi & 1.
+template <int H, bool BF16>
+__device__ __forceinline__ void fwd_issue_group(const void* PQ, const int* s, int wr, int gi, int g, unsigned colb,
+                                                unsigned (&wpo)[8], unsigned (&wqo)[8], float (&ddo)[8]) {
+  using C = ECfg<H, BF16>;
+  using PQP = PQPitch<H, true>;
+  const int rblk = wr * C::RB + (gi >> 1), vh = gi & 1;
+  int di[8], ci[8];
+  lds_rows8(s, rblk, vh, g, di);
+  lds_rows8(s + C::TM, rblk, vh, g, ci);
+  lds_rows8(s + 2 * C::TM, rblk, vh, g, ddo);
+#pragma unroll
+  for (int u = 0; u < 8; ++u) {
+    wpo[u] = ldg_u32(PQ, (unsigned)di[u] * PQP::ROW + colb);
+    wqo[u] = ldg_u32(PQ, (unsigned)ci[u] * PQP::ROW + colb + PQP::QOFF);
+  }
+}
+
 // One tile of the forward kernel. FULL: all TM edges of the tile exist (no masking anywhere).
+// wp0 / wq0 / dd0 (bf16 pairs only): the gathers of this tile's first group, asked for at the end of the previous
+// tile; on return they hold those of the next tile's first group.
 template <int H, bool BF16, bool BRES, bool FULL>
 __device__ __forceinline__ void edge_fwd_tile(
     const EdgeFwdArgs& p, unsigned char* smem, const int* s, int* s_next, int nxt, int tile, int E, int tid, int wr,
     int wc, int lane, const float (&w1d)[ECfg<H, BF16>::CB], const float (&b2)[ECfg<H, BF16>::CB],
-    const typename BFrag<H, BF16>::type (&breg)[BRES ? BFrag<H, BF16>::NKB : 1][ECfg<H, BF16>::CB]) {
+    const typename BFrag<H, BF16>::type (&breg)[BRES ? BFrag<H, BF16>::NKB : 1][ECfg<H, BF16>::CB],
+    unsigned (&wp0)[8], unsigned (&wq0)[8], float (&dd0)[8]) {
   using C = ECfg<H, BF16>;
   constexpr bool PAIRS = BF16 && C::CB == 2;
   const int g = lane >> 5, x = lane & 31;
@@ -342,29 +364,20 @@ __device__ __forceinline__ void edge_fwd_tile(
     // Groups of 8 edges, software-pipelined: the gathers of the next group are in flight while this one is turned
     // into a1 (the accumulator registers are free in this phase and hold the second set of gathered words; a third
     // set would spill).
-    using PQP = PQPitch<H, true>;
     constexpr int NG = C::RB * 2;
-    constexpr int NS = 2;
-    unsigned wp[NS][8], wq[NS][8];
-    float dd[NS][8];
-    auto issue = [&](int gi, unsigned (&wpo)[8], unsigned (&wqo)[8], float (&ddo)[8]) {
-      const int rblk = wr * C::RB + (gi >> 1), vh = gi & 1;
-      int di[8], ci[8];
-      lds_rows8(s, rblk, vh, g, di);
-      lds_rows8(s + C::TM, rblk, vh, g, ci);
-      lds_rows8(s + 2 * C::TM, rblk, vh, g, ddo);
-#pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        wpo[u] = ldg_u32(p.PQ, (unsigned)di[u] * PQP::ROW + colb);
-        wqo[u] = ldg_u32(p.PQ, (unsigned)ci[u] * PQP::ROW + colb + PQP::QOFF);
-      }
-    };
-#pragma unroll
-    for (int gi = 0; gi < NS - 1; ++gi) issue(gi, wp[gi], wq[gi], dd[gi]);
+    static_assert(NG % 2 == 0, "even groups use the carried buffers, odd ones the local set");
+    unsigned wp1[8], wq1[8];
+    float dd1[8];
 #pragma unroll
     for (int gi = 0; gi < NG; ++gi) {
-      if (gi + NS - 1 < NG) issue(gi + NS - 1, wp[(gi + NS - 1) % NS], wq[(gi + NS - 1) % NS], dd[(gi + NS - 1) % NS]);
-      const int sl = gi % NS;
+      // the first group's gathers were asked for at the end of the previous tile
+      if (gi + 1 < NG) {
+        if ((gi + 1) & 1) fwd_issue_group<H, BF16>(p.PQ, s, wr, gi + 1, g, colb, wp1, wq1, dd1);
+        else fwd_issue_group<H, BF16>(p.PQ, s, wr, gi + 1, g, colb, wp0, wq0, dd0);
+      }
+      const unsigned (&wpc)[8] = (gi & 1) ? wp1 : wp0;
+      const unsigned (&wqc)[8] = (gi & 1) ? wq1 : wq0;
+      const float (&ddc)[8] = (gi & 1) ? dd1 : dd0;
       const int rblk = wr * C::RB + (gi >> 1), vh = gi & 1;
       const int eb = tile * (C::TM / 32) + rblk;
 #pragma unroll
@@ -373,9 +386,9 @@ __device__ __forceinline__ void edge_fwd_tile(
         float vals[8];
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
-          const float zp = j == 0 ? __uint_as_float(wp[sl][u] << 16) : __uint_as_float(wp[sl][u] & 0xffff0000u);
-          const float zq = j == 0 ? __uint_as_float(wq[sl][u] << 16) : __uint_as_float(wq[sl][u] & 0xffff0000u);
-          vals[u] = silu_f(zp + zq + dd[sl][u] * w1d[j]);
+          const float zp = j == 0 ? __uint_as_float(wpc[u] << 16) : __uint_as_float(wpc[u] & 0xffff0000u);
+          const float zq = j == 0 ? __uint_as_float(wqc[u] << 16) : __uint_as_float(wqc[u] & 0xffff0000u);
+          vals[u] = silu_f(zp + zq + ddc[u] * w1d[j]);
         }
         emit_half<BF16, C::STRIDE>(smem, rblk * 32, g, cblk * 32 + x, vals, vh, p.a1_pk, (size_t)eb * C::NCB + cblk, lane);
       }
@@ -432,6 +445,9 @@ __device__ __forceinline__ void edge_fwd_tile(
 #pragma unroll
       for (int v = 0; v < 16; ++v)
         stg_nt<unsigned>(o, lane * 4u + v * 256u, pack_bf16x2(acc[i][0][v] + b2[0], acc[i][1][v] + b2[1]));
+      // the next tile's scalars are in LDS now: its first gathers travel behind the first block's stores, whose
+      // accumulators are free by then (past the last tile the scalars are zeros and the gathers read row 0)
+      if (FULL && i == 0) fwd_issue_group<H, BF16>(p.PQ, s_next, wr, 0, g, colb, wp0, wq0, dd0);
     } else {
 #pragma unroll
       for (int j = 0; j < C::CB; ++j) {
@@ -452,6 +468,7 @@ __device__ __forceinline__ void edge_fwd_tile(
       }
     }
   }
+  if constexpr (PAIRS && !FULL) fwd_issue_group<H, BF16>(p.PQ, s_next, wr, 0, g, colb, wp0, wq0, dd0);
 }
 
 template <int H, bool BF16, bool BRES_REQ>
@@ -480,6 +497,10 @@ __global__ void __launch_bounds__(256, 2) k_edge_fwd(EdgeFwdArgs p, int ntiles) 
     if (tid < 3 * C::TM) sc[tid] = s0;
   }
   __syncthreads();
+  unsigned wp0[8], wq0[8];   // bf16 pairs: gathers of the coming tile's first group (see edge_fwd_tile)
+  float dd0[8];
+  if constexpr (BF16 && C::CB == 2)
+    fwd_issue_group<H, BF16>(p.PQ, sc, wr, 0, lane >> 5, (unsigned)(wc * 32 + x) * 4u, wp0, wq0, dd0);
   int buf = 0;
   for (int tile = tr.first; tile < tr.end; tile += tr.step, buf ^= 1) {
     // the next tile's scalars travel while this tile is processed
@@ -487,9 +508,9 @@ __global__ void __launch_bounds__(256, 2) k_edge_fwd(EdgeFwdArgs p, int ntiles) 
     const int* s = sc + buf * 3 * C::TM;
     int* s_next = sc + (buf ^ 1) * 3 * C::TM;
     if ((tile + 1) * C::TM <= E)
-      edge_fwd_tile<H, BF16, BRES, true>(p, smem, s, s_next, nxt, tile, E, tid, wr, wc, lane, w1d, b2, breg);
+      edge_fwd_tile<H, BF16, BRES, true>(p, smem, s, s_next, nxt, tile, E, tid, wr, wc, lane, w1d, b2, breg, wp0, wq0, dd0);
     else
-      edge_fwd_tile<H, BF16, BRES, false>(p, smem, s, s_next, nxt, tile, E, tid, wr, wc, lane, w1d, b2, breg);
+      edge_fwd_tile<H, BF16, BRES, false>(p, smem, s, s_next, nxt, tile, E, tid, wr, wc, lane, w1d, b2, breg, wp0, wq0, dd0);
   }
 }
 
