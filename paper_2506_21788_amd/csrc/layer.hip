@@ -11,6 +11,7 @@
 #include "edge_fused.h"
 #include "edgeops.h"
 #include "gemm.h"
+#include "wide.h"
 
 namespace hgnn {
 
@@ -130,8 +131,10 @@ static int32_t check_layer_args(int N, int64_t E, int H, int dtype) {
   // the edge kernels gather rows of [N,2H] fp32 node tensors at 32-bit byte offsets
   HGNN_REQUIRE((int64_t)N * 2 * H * 4 < (1ll << 32), HGNN_ERR_OVERFLOW,
                "N * 2H * 4 bytes must stay below 4 GiB (N = %d, H = %d)", N, H);
-  HGNN_REQUIRE(valid_H(H), HGNN_ERR_BAD_SHAPE, "H must be 64, 128 or 256 (got %d)", H);
   HGNN_REQUIRE(dtype == HGNN_F32 || dtype == HGNN_BF16, HGNN_ERR_BAD_SHAPE, "unknown dtype %d", dtype);
+  HGNN_REQUIRE(valid_H(H) || wide_H(H), HGNN_ERR_BAD_SHAPE, "H must be 64, 128, 256 or lie in 257..1024 (got %d)", H);
+  HGNN_REQUIRE(!wide_H(H) || dtype == HGNN_BF16, HGNN_ERR_UNIMPLEMENTED,
+               "widths above 256 run with bf16 operands only (H = %d)", H);
   return HGNN_OK;
 }
 
@@ -149,6 +152,10 @@ extern "C" int32_t hgnn_mp_layer_workspace_bytes(int32_t N, int64_t E, int32_t H
                                                  size_t* ws_bytes_host, size_t* saved_bytes_host) {
   HGNN_TRY(check_layer_args(N, E, H, dtype));
   HGNN_REQUIRE(ws_bytes_host && saved_bytes_host, HGNN_ERR_NULLPTR, "null size pointer");
+  if (wide_H(H)) {
+    wide_layer_sizes(N, E, H, ws_bytes_host, saved_bytes_host);
+    return HGNN_OK;
+  }
   *ws_bytes_host = carve_ws(nullptr, N, E, H, dtype == HGNN_BF16).bytes;
   *saved_bytes_host = carve_saved(nullptr, N, E, H, dtype == HGNN_BF16).bytes;
   return HGNN_OK;
@@ -167,6 +174,18 @@ extern "C" int32_t hgnn_mp_layer_fwd(void* stream, int32_t N, int64_t E, int32_t
   HGNN_REQUIRE(saved != nullptr, HGNN_ERR_UNIMPLEMENTED,
                "mp_layer_fwd without a saved buffer (recompute in backward) is not implemented");
   HGNN_REQUIRE(h_out != h_in, HGNN_ERR_BAD_SHAPE, "h_out may not alias h_in");
+  if (wide_H(H)) {
+    size_t need_ws, need_saved;
+    wide_layer_sizes(N, E, H, &need_ws, &need_saved);
+    HGNN_REQUIRE(ws_bytes >= need_ws, HGNN_ERR_WORKSPACE_TOO_SMALL, "mp_layer workspace: need %zu bytes, got %zu", need_ws, ws_bytes);
+    HGNN_REQUIRE(saved_bytes >= need_saved, HGNN_ERR_WORKSPACE_TOO_SMALL, "mp_layer saved buffer: need %zu bytes, got %zu", need_saved, saved_bytes);
+    WideLayerArgs a;
+    a.N = N; a.E = E; a.H = H; a.alpha = alpha;
+    a.row_ptr = row_ptr; a.dst = dst; a.col = col; a.d2 = d2; a.rvec = rvec;
+    a.h_in = h_in; a.v_in = v_in; a.W = W; a.h_out = h_out; a.v_out = v_out;
+    a.saved = saved; a.ws = ws;
+    return wide_layer_fwd(st, a);
+  }
   const bool bf16 = dtype == HGNN_BF16;
   LayerWs w = carve_ws(ws, N, E, H, bf16);
   LayerSaved s = carve_saved(saved, N, E, H, bf16);
@@ -247,6 +266,19 @@ extern "C" int32_t hgnn_mp_layer_bwd(void* stream, int32_t N, int64_t E, int32_t
   HGNN_REQUIRE(E == 0 || (dst && col && d2 && rvec && permT), HGNN_ERR_NULLPTR, "mp_layer_bwd: null edge array");
   HGNN_REQUIRE(N == 0 || g_h_in != g_h_out, HGNN_ERR_BAD_SHAPE, "g_h_in may not alias g_h_out");
   if (N == 0) return launch_fill_f32(st, gW, LayerOff(H).total, 0.f);
+  if (wide_H(H)) {
+    size_t need_ws, need_saved;
+    wide_layer_sizes(N, E, H, &need_ws, &need_saved);
+    HGNN_REQUIRE(ws_bytes >= need_ws, HGNN_ERR_WORKSPACE_TOO_SMALL, "mp_layer workspace: need %zu bytes, got %zu", need_ws, ws_bytes);
+    HGNN_REQUIRE(saved_bytes >= need_saved, HGNN_ERR_WORKSPACE_TOO_SMALL, "mp_layer saved buffer: need %zu bytes, got %zu", need_saved, saved_bytes);
+    WideLayerArgs a;
+    a.N = N; a.E = E; a.H = H; a.alpha = alpha;
+    a.row_ptr = row_ptr; a.dst = dst; a.col = col; a.d2 = d2; a.rvec = rvec;
+    a.colT_ptr = colT_ptr; a.permT = permT;
+    a.h_in = h_in; a.W = W; a.g_h_out = g_h_out; a.g_v_out = g_v_out; a.g_h_in = g_h_in; a.g_v_in = g_v_in; a.gW = gW;
+    a.saved = const_cast<void*>(saved); a.ws = ws;
+    return wide_layer_bwd(st, a);
+  }
   const bool bf16 = dtype == HGNN_BF16;
   LayerWs w = carve_ws(ws, N, E, H, bf16);
   LayerSaved s = carve_saved(const_cast<void*>(saved), N, E, H, bf16);

@@ -1,0 +1,1104 @@
+// Message-passing layer for hidden widths above 256 (see wide.h for the operand layouts):
+//   k_fgemm        one kernel for every product: out[i][j] += A(i, kb) x B(j, kb) over 1 KiB fragments staged through
+//                  LDS; epilogues: result as T fragments (edge tensors), row-major fp32 / bf16 with bias and
+//                  residuals (atom tensors), fp32 split partials (weight gradients)
+//   k_pack_frag    fp32 weight slices -> B fragments (zero padded)
+//   k_to_frag      row-major fp32 atom tensor -> R and / or T fragments (optionally silu(x) or x * silu'(z))
+//   k_edge_a1      a1 = silu(P[dst] + Q[col] + d2 w1d)                          -> R and T
+//   k_seg_fwd_w    M_i = alpha sum silu(z2), v'_i = v_i + alpha sum (wx . m_e) rvec_e   (one wavefront per atom)
+//   k_edge_gz2     g_z2 = (alpha g_M[dst] + c_e wx) silu'(z2) -> R and T, with the column sums for g_b2, g_wx
+//   k_edge_gz1     g_z1 = g_a1 silu'(z1) in place (T), with the column sums for g_b1, g_w1d
+//   k_segsum_w     per-atom sums of g_z1 rows over the destination-sorted or source-sorted edge lists
+// The layer follows the same algebra as the narrow path: the first edge layer is split by linearity into per-atom
+// products P = h W1a + b1, Q = h W1b that the edges gather.
+#include "wide.h"
+
+#include "devmath.h"
+#include "edge_fused.h"
+#include "edgeops.h"
+
+namespace hgnn {
+
+enum { EPI_T = 0, EPI_ROW = 1, EPI_PART = 2 };
+
+// row of slot u of lane half g in the 16-row group rb16 (the accumulator layout of the 32x32 matrix-core tile)
+__device__ __forceinline__ int tset_row(int rb16, int g, int u) { return rb16 * 16 + 8 * (u >> 2) + 4 * g + (u & 3); }
+__device__ __forceinline__ float bf_lo(unsigned w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf_hi(unsigned w) { return __uint_as_float(w & 0xffff0000u); }
+
+// ---------------------------------------------------------------------------------------------
+// fragment GEMM
+// ---------------------------------------------------------------------------------------------
+struct FGemmArgs {
+  const char* A = nullptr;   // fragment (i, kb) at A + (i * a_si + kb * a_sk) KiB
+  long a_si = 0, a_sk = 0;
+  const char* B = nullptr;
+  long b_sj = 0, b_sk = 0;
+  int nI = 0, nJ = 0;        // 32-blocks of the two free dimensions (multiples of the workgroup tile)
+  int nkb = 0;               // 16-blocks of the contraction (even)
+  int kper = 0;              // per split (even)
+  int nsplit = 1;
+  // EPI_T: bf16 T fragments, t_ncb column blocks per row group
+  char* T = nullptr;
+  int t_ncb = 0;
+  // EPI_ROW
+  int M = 0;                 // valid rows
+  float* Cf = nullptr;       // fp32 out, columns < ncol_f
+  long ldc = 0;
+  int ncol_f = 0;
+  unsigned short* Cb = nullptr;   // bf16 out, all columns of the tile
+  long ldcb = 0;
+  const float* r1 = nullptr;      // residuals added to Cf (columns < ncol_f)
+  long ld1 = 0;
+  const float* r2 = nullptr;
+  long ld2 = 0;
+  // EPI_T and EPI_ROW: bias[col] for col < nbias
+  const float* bias = nullptr;
+  int nbias = 0;
+  // EPI_PART: fp32 partial[split][row][col]
+  float* P = nullptr;
+  long ldp = 0, split_stride = 0;
+  int tag = PT_GEMM_NODE;
+};
+
+template <int WI, int WJ>
+struct FCfg {
+  static constexpr int KC = 2;               // contraction blocks staged per step
+  static constexpr int TI = 2 * WI, TJ = 2 * WJ;
+  static constexpr int NF = KC * (TI + TJ);  // fragments per step
+  static constexpr int PASSES = NF / 4;      // each wavefront copies one fragment per pass
+  static constexpr int LDS_BYTES = NF * 1024;
+  static_assert(NF % 4 == 0, "fragments per step must divide among four wavefronts");
+};
+
+template <int WI, int WJ, int EPI>
+__global__ void __launch_bounds__(256, (WI * WJ <= 8 ? 2 : 1)) k_fgemm(FGemmArgs p) {
+  using C = FCfg<WI, WJ>;
+  extern __shared__ __align__(16) uint4 lds[];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wi = wave >> 1, wj = wave & 1;
+  const int i0 = blockIdx.y * C::TI, j0 = blockIdx.x * C::TJ;
+  const int kbeg = blockIdx.z * p.kper;
+  const int kend = kbeg + p.kper < p.nkb ? kbeg + p.kper : p.nkb;
+
+  // pass s copies fragment f = 4 s + wave of the step: first the KC x TI fragments of A, then the KC x TJ of B
+  const char* src[C::PASSES];
+  long kst[C::PASSES];
+#pragma unroll
+  for (int s = 0; s < C::PASSES; ++s) {
+    const int f = 4 * s + wave;
+    if (f < C::KC * C::TI) {
+      const int kk = f / C::TI, ii = f % C::TI;
+      src[s] = p.A + ((long)(i0 + ii) * p.a_si + (long)kk * p.a_sk) * 1024 + lane * 16;
+      kst[s] = p.a_sk * 1024;
+    } else {
+      const int f2 = f - C::KC * C::TI;
+      const int kk = f2 / C::TJ, jj = f2 % C::TJ;
+      src[s] = p.B + ((long)(j0 + jj) * p.b_sj + (long)kk * p.b_sk) * 1024 + lane * 16;
+      kst[s] = p.b_sk * 1024;
+    }
+  }
+  uint4 pre[C::PASSES];
+  auto fetch = [&](int kb) {
+#pragma unroll
+    for (int s = 0; s < C::PASSES; ++s) pre[s] = *reinterpret_cast<const uint4*>(src[s] + (long)kb * kst[s]);
+  };
+
+  f32x16_t acc[WI][WJ];
+#pragma unroll
+  for (int i = 0; i < WI; ++i)
+#pragma unroll
+    for (int j = 0; j < WJ; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  if (kbeg < kend) fetch(kbeg);
+  for (int kb = kbeg; kb < kend; kb += C::KC) {
+    __syncthreads();   // the previous step's fragments have been consumed
+#pragma unroll
+    for (int s = 0; s < C::PASSES; ++s) lds[(4 * s + wave) * 64 + lane] = pre[s];
+    __syncthreads();
+    if (kb + C::KC < kend) fetch(kb + C::KC);   // the next step travels during the products
+#pragma unroll
+    for (int kk = 0; kk < C::KC; ++kk) {
+      bf16x8_t a[WI], b[WJ];
+#pragma unroll
+      for (int i = 0; i < WI; ++i) {
+        const uint4 w = lds[(kk * C::TI + wi * WI + i) * 64 + lane];
+        a[i] = *reinterpret_cast<const bf16x8_t*>(&w);
+      }
+#pragma unroll
+      for (int j = 0; j < WJ; ++j) {
+        const uint4 w = lds[(C::KC * C::TI + kk * C::TJ + wj * WJ + j) * 64 + lane];
+        b[j] = *reinterpret_cast<const bf16x8_t*>(&w);
+      }
+#pragma unroll
+      for (int i = 0; i < WI; ++i)
+#pragma unroll
+        for (int j = 0; j < WJ; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+    }
+  }
+
+  // accumulator register v of lane (g, x): row 8 (v >> 2) + 4 g + (v & 3), column x of the 32 x 32 block
+  const int g = lane >> 5, x = lane & 31;
+#pragma unroll
+  for (int j = 0; j < WJ; ++j) {
+    const int jb = j0 + wj * WJ + j;
+    const int colx = jb * 32 + x;
+    float bv = 0.f;
+    if (EPI != EPI_PART && p.bias && colx < p.nbias) bv = p.bias[colx];
+#pragma unroll
+    for (int i = 0; i < WI; ++i) {
+      const int ib = i0 + wi * WI + i;
+      if constexpr (EPI == EPI_T) {
+#pragma unroll
+        for (int hh = 0; hh < 2; ++hh) {
+          uint4 w;
+          w.x = pack_bf16x2(acc[i][j][8 * hh + 0] + bv, acc[i][j][8 * hh + 1] + bv);
+          w.y = pack_bf16x2(acc[i][j][8 * hh + 2] + bv, acc[i][j][8 * hh + 3] + bv);
+          w.z = pack_bf16x2(acc[i][j][8 * hh + 4] + bv, acc[i][j][8 * hh + 5] + bv);
+          w.w = pack_bf16x2(acc[i][j][8 * hh + 6] + bv, acc[i][j][8 * hh + 7] + bv);
+          *reinterpret_cast<uint4*>(p.T + ((long)(2 * ib + hh) * p.t_ncb + jb) * 1024 + lane * 16) = w;
+        }
+      } else if constexpr (EPI == EPI_ROW) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int row = ib * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
+          if (row < p.M) {
+            float val = acc[i][j][v] + bv;
+            if (p.Cf && colx < p.ncol_f) {
+              if (p.r1) val += p.r1[(long)row * p.ld1 + colx];
+              if (p.r2) val += p.r2[(long)row * p.ld2 + colx];
+              p.Cf[(long)row * p.ldc + colx] = val;
+            }
+            if (p.Cb) p.Cb[(long)row * p.ldcb + colx] = (unsigned short)f2bf_bits(val);
+          }
+        }
+      } else {
+        float* out = p.P + (long)blockIdx.z * p.split_stride;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int row = ib * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
+          out[(long)row * p.ldp + colx] = acc[i][j][v];
+        }
+      }
+    }
+  }
+}
+
+template <int WI, int WJ, int EPI>
+static int32_t launch_fgemm_t(hipStream_t st, const FGemmArgs& a) {
+  using C = FCfg<WI, WJ>;
+  HGNN_REQUIRE(a.nI % C::TI == 0 && a.nJ % C::TJ == 0 && a.nkb % C::KC == 0 && a.kper % C::KC == 0 && a.kper > 0,
+               HGNN_ERR_BAD_SHAPE, "fragment GEMM: %d x %d blocks, %d contraction blocks do not tile", a.nI, a.nJ, a.nkb);
+  if (a.nI == 0 || a.nJ == 0) return HGNN_OK;
+  const int nsplit = a.nkb == 0 ? 1 : (a.nkb + a.kper - 1) / a.kper;
+  HGNN_REQUIRE(nsplit == a.nsplit, HGNN_ERR_BAD_SHAPE, "fragment GEMM: split count mismatch");
+  HGNN_REQUIRE(a.nI / C::TI <= 65535 && nsplit <= 65535, HGNN_ERR_OVERFLOW, "fragment GEMM: grid too large");
+  ProfScope ps(a.tag, st);
+  k_fgemm<WI, WJ, EPI><<<dim3(a.nJ / C::TJ, a.nI / C::TI, nsplit), 256, C::LDS_BYTES, st>>>(a);
+  HGNN_LAUNCH_CHECK("k_fgemm");
+  return HGNN_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// weights -> B fragments:  fragment (nb, kb) of the destination, lane (g, x), slot u  =  B[16 kb + 8 g + u][32 nb + x]
+// ---------------------------------------------------------------------------------------------
+struct PackPart {
+  long src_off;        // B[k][n] = src[src_off + k * sk + n * sn] for k < K, n < Nn, else 0
+  int sk, sn;
+  int kb0, nb0;        // where the part's (Hp/16 x Hp/32) fragments sit in the destination
+};
+struct PackFragArgs {
+  const float* src;
+  unsigned short* dst;
+  int nkb_total;       // fragments per column block of the destination
+  int K, Nn;           // valid extent of every part
+  int Hp;
+  int nparts;
+  PackPart part[4];
+};
+
+__global__ void __launch_bounds__(256) k_pack_frag(PackFragArgs a) {
+  const PackPart pt = a.part[blockIdx.y];
+  const long idx = (long)blockIdx.x * 256 + threadIdx.x;   // element of the part: [nb][kb][lane][u]
+  const int nkb = a.Hp / 16;
+  if (idx >= (long)a.Hp * a.Hp) return;
+  const int u = idx & 7, lane = (idx >> 3) & 63;
+  const int f = (int)(idx >> 9);
+  const int kb = f % nkb, nb = f / nkb;
+  const int k = kb * 16 + (lane >> 5) * 8 + u, n = nb * 32 + (lane & 31);
+  float v = 0.f;
+  if (k < a.K && n < a.Nn) v = a.src[pt.src_off + (long)k * pt.sk + (long)n * pt.sn];
+  a.dst[(((long)(pt.nb0 + nb) * a.nkb_total + pt.kb0 + kb) * 64 + lane) * 8 + u] = (unsigned short)f2bf_bits(v);
+}
+
+static int32_t launch_pack_frag(hipStream_t st, const PackFragArgs& a) {
+  ProfScope ps(PT_PACK, st);
+  k_pack_frag<<<dim3((unsigned)(((long)a.Hp * a.Hp + 255) / 256), a.nparts), 256, 0, st>>>(a);
+  HGNN_LAUNCH_CHECK("k_pack_frag");
+  return HGNN_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// row-major fp32 -> fragments.  mode 0: x, 1: silu(x), 2: x * silu'(z)
+// ---------------------------------------------------------------------------------------------
+struct ToFragArgs {
+  const float* X = nullptr;
+  long ldx = 0;
+  const float* Z = nullptr;
+  long ldz = 0;
+  int mode = 0;
+  int M = 0;          // valid rows
+  int Mp = 0;         // rows covered (multiple of 32), rows >= M give zeros
+  int ncol = 0;       // valid columns
+  int Cp = 0;         // columns covered (multiple of 32), columns >= ncol give zeros
+  char* R = nullptr;  // R fragments: r_nkb contraction blocks per row block, this tensor starts at block r_kb0
+  int r_nkb = 0, r_kb0 = 0;
+  char* T = nullptr;  // T fragments: t_ncb column blocks per row group, this tensor starts at block t_cb0
+  int t_ncb = 0, t_cb0 = 0;
+};
+
+__global__ void __launch_bounds__(256) k_to_frag(ToFragArgs a) {
+  const int CG = a.Cp >> 3;
+  const long idx = (long)blockIdx.x * 256 + threadIdx.x;
+  const int cg = (int)(idx % CG);
+  const long rs = idx / CG;   // row set: 16-row group rs >> 1, lane half rs & 1
+  if (rs >= a.Mp / 8) return;
+  const int rb16 = (int)(rs >> 1), g = (int)(rs & 1);
+  const int c0 = cg * 8;
+  unsigned short vals[8][8];   // [u][k]
+#pragma unroll
+  for (int u = 0; u < 8; ++u) {
+    const int r = tset_row(rb16, g, u);
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      float v = 0.f;
+      if (r < a.M && c0 + k < a.ncol) {
+        v = a.X[(long)r * a.ldx + c0 + k];
+        if (a.mode == 1) v = silu_f(v);
+        else if (a.mode == 2) v *= dsilu_f(a.Z[(long)r * a.ldz + c0 + k]);
+      }
+      vals[u][k] = (unsigned short)f2bf_bits(v);
+    }
+  }
+  if (a.R) {
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int r = tset_row(rb16, g, u);
+      uint4 w;
+      w.x = vals[u][0] | ((unsigned)vals[u][1] << 16);
+      w.y = vals[u][2] | ((unsigned)vals[u][3] << 16);
+      w.z = vals[u][4] | ((unsigned)vals[u][5] << 16);
+      w.w = vals[u][6] | ((unsigned)vals[u][7] << 16);
+      const long frag = (long)(r >> 5) * a.r_nkb + a.r_kb0 + (c0 >> 4);
+      *reinterpret_cast<uint4*>(a.R + (frag * 64 + ((c0 >> 3) & 1) * 32 + (r & 31)) * 16) = w;
+    }
+  }
+  if (a.T) {
+    const long frag = (long)rb16 * a.t_ncb + a.t_cb0 + (c0 >> 5);
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      uint4 w;
+      w.x = vals[0][k] | ((unsigned)vals[1][k] << 16);
+      w.y = vals[2][k] | ((unsigned)vals[3][k] << 16);
+      w.z = vals[4][k] | ((unsigned)vals[5][k] << 16);
+      w.w = vals[6][k] | ((unsigned)vals[7][k] << 16);
+      *reinterpret_cast<uint4*>(a.T + (frag * 64 + g * 32 + (c0 & 31) + k) * 16) = w;
+    }
+  }
+}
+
+static int32_t launch_to_frag(hipStream_t st, const ToFragArgs& a) {
+  HGNN_REQUIRE(a.Mp % 32 == 0 && a.Cp % 32 == 0, HGNN_ERR_BAD_SHAPE, "to_frag: padded extents must be multiples of 32");
+  const long n = (long)(a.Mp / 8) * (a.Cp / 8);
+  if (n == 0) return HGNN_OK;
+  ProfScope ps(PT_MISC, st);
+  k_to_frag<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(a);
+  HGNN_LAUNCH_CHECK("k_to_frag");
+  return HGNN_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// column sums of small row-major tensors and ordered reduction of per-block partial rows
+// ---------------------------------------------------------------------------------------------
+// dest[c] = sum over s < nsplit (ascending) of partial[s * stride + c], c < ncol
+__global__ void __launch_bounds__(256) k_reduce_cols(const float* __restrict__ partial, int nsplit, long stride,
+                                                     int ncol, float* __restrict__ dest) {
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= ncol) return;
+  float s = 0.f;
+  for (int k = 0; k < nsplit; ++k) s += partial[(long)k * stride + c];
+  dest[c] = s;
+}
+static int32_t launch_reduce_cols(hipStream_t st, const float* partial, int nsplit, long stride, int ncol, float* dest) {
+  k_reduce_cols<<<(ncol + 255) / 256, 256, 0, st>>>(partial, nsplit, stride, ncol, dest);
+  HGNN_LAUNCH_CHECK("k_reduce_cols");
+  return HGNN_OK;
+}
+
+constexpr int CS_ROWS = 64;   // rows per partial of k_colsum_rows
+// partial[split][c] = sum over the split's rows of f(X[r][c]);  mode as in k_to_frag
+__global__ void __launch_bounds__(256) k_colsum_rows(const float* __restrict__ X, long ldx, const float* __restrict__ Z,
+                                                     long ldz, int mode, int M, int ncol, float* __restrict__ partial,
+                                                     long stride) {
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= ncol) return;
+  const int r0 = blockIdx.y * CS_ROWS;
+  const int r1 = r0 + CS_ROWS < M ? r0 + CS_ROWS : M;
+  float s = 0.f;
+  for (int r = r0; r < r1; ++r) {
+    float v = X[(long)r * ldx + c];
+    if (mode == 1) v = silu_f(v);
+    else if (mode == 2) v *= dsilu_f(Z[(long)r * ldz + c]);
+    s += v;
+  }
+  partial[(long)blockIdx.y * stride + c] = s;
+}
+static size_t colsum_rows_partial_floats(int M, int Hp) { return (size_t)((M + CS_ROWS - 1) / CS_ROWS + 1) * Hp; }
+static int32_t launch_colsum_rows(hipStream_t st, const float* X, long ldx, const float* Z, long ldz, int mode, int M,
+                                  int ncol, int Hp, float* partial, float* dest) {
+  ProfScope ps(PT_COLSUM, st);
+  const int ns = (M + CS_ROWS - 1) / CS_ROWS;
+  if (ns > 0) {
+    k_colsum_rows<<<dim3((ncol + 255) / 256, ns), 256, 0, st>>>(X, ldx, Z, ldz, mode, M, ncol, partial, Hp);
+    HGNN_LAUNCH_CHECK("k_colsum_rows");
+  }
+  return launch_reduce_cols(st, partial, ns, Hp, ncol, dest);
+}
+
+// dest[pa * strideA + pb * strideB + r1 * H + r2] = sum over splits (ascending) of partial[s][k1][k2],
+// k1 = pa * Hp + r1, k2 = pb * Hp + r2; padding rows / columns (r >= H) are dropped
+__global__ void __launch_bounds__(256) k_reduce_wgrad(const float* __restrict__ partial, int nsplit, long split_stride,
+                                                      int K1p, int K2p, int Hp, int H, float* __restrict__ dest,
+                                                      long strideA, long strideB) {
+  const long idx = (long)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (long)K1p * K2p) return;
+  const int k1 = (int)(idx / K2p), k2 = (int)(idx % K2p);
+  const int pa = k1 / Hp, r1 = k1 % Hp, pb = k2 / Hp, r2 = k2 % Hp;
+  if (r1 >= H || r2 >= H) return;
+  float s = 0.f;
+  for (int k = 0; k < nsplit; ++k) s += partial[(long)k * split_stride + idx];
+  dest[pa * strideA + pb * strideB + (long)r1 * H + r2] = s;
+}
+
+// ---------------------------------------------------------------------------------------------
+// edge kernels on 8 x 8 micro-blocks: 8 rows of one row set (T order) x 8 consecutive columns per thread
+// ---------------------------------------------------------------------------------------------
+struct EdgeElemArgs {
+  int64_t E = 0;
+  long nrs = 0;            // row sets covered (padded rows / 8)
+  int H = 0, Hp = 0;
+  const int32_t* dst = nullptr;
+  const int32_t* col = nullptr;
+  const float* d2 = nullptr;
+  const unsigned short* PQ = nullptr;   // [N, 2 Hp] bf16 row-major: P | Q
+  const float* w1d = nullptr;           // [H]
+  char* a1_R = nullptr;
+  char* a1_T = nullptr;
+  // reverse
+  const char* z2_T = nullptr;
+  const unsigned short* gM = nullptr;   // bf16 row-major g_M, row pitch ldgM elements
+  long ldgM = 0;
+  const float* cvec = nullptr;
+  const float* wx = nullptr;            // [H]
+  float alpha = 1.f;
+  char* gz2_R = nullptr;
+  char* gz2_T = nullptr;
+  char* ga1_T = nullptr;                // g_a1 in, g_z1 out (in place)
+  float* colpart = nullptr;             // [blocks][2][Hp] column-sum partials
+};
+
+__device__ __forceinline__ void unpack8(const uint4 w, float (&f)[8]) {
+  f[0] = bf_lo(w.x); f[1] = bf_hi(w.x); f[2] = bf_lo(w.y); f[3] = bf_hi(w.y);
+  f[4] = bf_lo(w.z); f[5] = bf_hi(w.z); f[6] = bf_lo(w.w); f[7] = bf_hi(w.w);
+}
+__device__ __forceinline__ uint4 pack8(const float (&f)[8]) {
+  uint4 w;
+  w.x = pack_bf16x2(f[0], f[1]); w.y = pack_bf16x2(f[2], f[3]);
+  w.z = pack_bf16x2(f[4], f[5]); w.w = pack_bf16x2(f[6], f[7]);
+  return w;
+}
+// stores of one micro-block v[u][k] (row slot u, column c0 + k)
+__device__ __forceinline__ void store_R(char* R, int nkb, int rb16, int g, int c0, const float (&v)[8][8]) {
+#pragma unroll
+  for (int u = 0; u < 8; ++u) {
+    const int r = tset_row(rb16, g, u);
+    const long frag = (long)(r >> 5) * nkb + (c0 >> 4);
+    *reinterpret_cast<uint4*>(R + (frag * 64 + ((c0 >> 3) & 1) * 32 + (r & 31)) * 16) = pack8(v[u]);
+  }
+}
+__device__ __forceinline__ void store_T(char* T, int ncb, int rb16, int g, int c0, const float (&v)[8][8]) {
+  const long frag = (long)rb16 * ncb + (c0 >> 5);
+#pragma unroll
+  for (int k = 0; k < 8; ++k) {
+    float col[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) col[u] = v[u][k];
+    *reinterpret_cast<uint4*>(T + (frag * 64 + g * 32 + (c0 & 31) + k) * 16) = pack8(col);
+  }
+}
+__device__ __forceinline__ void load_T(const char* T, int ncb, int rb16, int g, int c0, float (&v)[8][8]) {
+  const long frag = (long)rb16 * ncb + (c0 >> 5);
+#pragma unroll
+  for (int k = 0; k < 8; ++k) {
+    float col[8];
+    unpack8(*reinterpret_cast<const uint4*>(T + (frag * 64 + g * 32 + (c0 & 31) + k) * 16), col);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u][k] = col[u];
+  }
+}
+
+// z1 of the micro-block from the gathered atom projections; rows past E give zeros
+__device__ __forceinline__ void gather_z1(const EdgeElemArgs& p, int rb16, int g, int c0, const float (&w1)[8],
+                                          float (&z)[8][8], bool (&ok)[8]) {
+#pragma unroll
+  for (int u = 0; u < 8; ++u) {
+    const long r = tset_row(rb16, g, u);
+    ok[u] = r < p.E;
+    const long rr = ok[u] ? r : 0;
+    const long di = ok[u] ? p.dst[rr] : 0, ci = ok[u] ? p.col[rr] : 0;
+    const float dd = ok[u] ? p.d2[rr] : 0.f;
+    float pf[8], qf[8];
+    unpack8(*reinterpret_cast<const uint4*>(p.PQ + di * 2 * p.Hp + c0), pf);
+    unpack8(*reinterpret_cast<const uint4*>(p.PQ + ci * 2 * p.Hp + p.Hp + c0), qf);
+#pragma unroll
+    for (int k = 0; k < 8; ++k) z[u][k] = pf[k] + qf[k] + dd * w1[k];
+  }
+}
+
+__global__ void __launch_bounds__(256) k_edge_a1(EdgeElemArgs p) {
+  const int CG = p.Hp >> 3;
+  const long idx = (long)blockIdx.x * 256 + threadIdx.x;
+  const int cg = (int)(idx % CG);
+  const long rs = idx / CG;
+  if (rs >= p.nrs) return;
+  const int rb16 = (int)(rs >> 1), g = (int)(rs & 1), c0 = cg * 8;
+  float w1[8];
+#pragma unroll
+  for (int k = 0; k < 8; ++k) w1[k] = c0 + k < p.H ? p.w1d[c0 + k] : 0.f;
+  float z[8][8];
+  bool ok[8];
+  gather_z1(p, rb16, g, c0, w1, z, ok);
+#pragma unroll
+  for (int u = 0; u < 8; ++u)
+#pragma unroll
+    for (int k = 0; k < 8; ++k) z[u][k] = ok[u] ? silu_f(z[u][k]) : 0.f;
+  store_R(p.a1_R, p.Hp / 16, rb16, g, c0, z);
+  store_T(p.a1_T, p.Hp / 32, rb16, g, c0, z);
+}
+
+// The two reverse kernels run blocks of (Hp / 8) x RS threads (column group x row set) that walk the row sets with a
+// grid stride and leave per-block column sums: colpart[block][0 / 1][Hp].
+__device__ __forceinline__ void write_colpart(float* sh, float* colpart, int Hp, const float (&s0)[8], const float (&s1)[8]) {
+  // sh: [blockDim.y][2][Hp]
+  const int c0 = threadIdx.x * 8;
+  float* mine = sh + (long)threadIdx.y * 2 * Hp;
+#pragma unroll
+  for (int k = 0; k < 8; ++k) {
+    mine[c0 + k] = s0[k];
+    mine[Hp + c0 + k] = s1[k];
+  }
+  __syncthreads();
+  if (threadIdx.y == 0) {
+    float* out = colpart + (long)blockIdx.x * 2 * Hp;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      float a = 0.f, b = 0.f;
+      for (int y = 0; y < (int)blockDim.y; ++y) {   // row sets of the block in order
+        a += sh[(long)y * 2 * Hp + c0 + k];
+        b += sh[(long)y * 2 * Hp + Hp + c0 + k];
+      }
+      out[c0 + k] = a;
+      out[Hp + c0 + k] = b;
+    }
+  }
+}
+
+// g_z2 = (alpha g_M[dst] + c_e wx) silu'(z2); column sums: [0] g_b2 = sum g_z2, [1] g_wx = sum c_e silu(z2)
+__global__ void __launch_bounds__(256) k_edge_gz2(EdgeElemArgs p) {
+  extern __shared__ float sh[];
+  const int c0 = threadIdx.x * 8;
+  float wxv[8];
+#pragma unroll
+  for (int k = 0; k < 8; ++k) wxv[k] = c0 + k < p.H ? p.wx[c0 + k] : 0.f;
+  float s0[8] = {}, s1[8] = {};
+  for (long rs = (long)blockIdx.x * blockDim.y + threadIdx.y; rs < p.nrs; rs += (long)gridDim.x * blockDim.y) {
+    const int rb16 = (int)(rs >> 1), g = (int)(rs & 1);
+    float z[8][8];
+    load_T(p.z2_T, p.Hp / 32, rb16, g, c0, z);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const long r = tset_row(rb16, g, u);
+      const bool ok = r < p.E;
+      const long di = ok ? p.dst[r] : 0;
+      const float cc = ok ? p.cvec[r] : 0.f;
+      float gm[8];
+      unpack8(*reinterpret_cast<const uint4*>(p.gM + di * p.ldgM + c0), gm);
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        float y, dy;
+        silu_both(z[u][k], y, dy);
+        const float gz = ok ? fmaf(cc, wxv[k], p.alpha * gm[k]) * dy : 0.f;
+        s0[k] += gz;
+        s1[k] += ok ? cc * y : 0.f;
+        z[u][k] = gz;
+      }
+    }
+    store_R(p.gz2_R, p.Hp / 16, rb16, g, c0, z);
+    store_T(p.gz2_T, p.Hp / 32, rb16, g, c0, z);
+  }
+  write_colpart(sh, p.colpart, p.Hp, s0, s1);
+}
+
+// g_z1 = g_a1 silu'(z1) (in place, T); column sums: [0] g_b1 = sum g_z1, [1] g_w1d = sum d2_e g_z1
+__global__ void __launch_bounds__(256) k_edge_gz1(EdgeElemArgs p) {
+  extern __shared__ float sh[];
+  const int c0 = threadIdx.x * 8;
+  float w1[8];
+#pragma unroll
+  for (int k = 0; k < 8; ++k) w1[k] = c0 + k < p.H ? p.w1d[c0 + k] : 0.f;
+  float s0[8] = {}, s1[8] = {};
+  for (long rs = (long)blockIdx.x * blockDim.y + threadIdx.y; rs < p.nrs; rs += (long)gridDim.x * blockDim.y) {
+    const int rb16 = (int)(rs >> 1), g = (int)(rs & 1);
+    float z[8][8], ga[8][8];
+    bool ok[8];
+    gather_z1(p, rb16, g, c0, w1, z, ok);
+    load_T(p.ga1_T, p.Hp / 32, rb16, g, c0, ga);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const long r = tset_row(rb16, g, u);
+      const float dd = ok[u] ? p.d2[r] : 0.f;
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        const float gz = ok[u] ? ga[u][k] * dsilu_f(z[u][k]) : 0.f;
+        s0[k] += gz;
+        s1[k] += dd * gz;
+        ga[u][k] = gz;
+      }
+    }
+    store_T(p.ga1_T, p.Hp / 32, rb16, g, c0, ga);
+  }
+  write_colpart(sh, p.colpart, p.Hp, s0, s1);
+}
+
+constexpr int ELEM_MAX_BLOCKS = 1024;   // per-block column-sum partials kept by the reverse edge kernels
+static dim3 elem_block(int Hp) { return dim3(Hp / 8, 256 / (Hp / 8) > 0 ? 256 / (Hp / 8) : 1); }
+static int elem_grid(long nrs, int Hp) {
+  const long per = elem_block(Hp).y;
+  const long need = (nrs + per - 1) / per;
+  return (int)(need < ELEM_MAX_BLOCKS ? (need < 1 ? 1 : need) : ELEM_MAX_BLOCKS);
+}
+
+// ---------------------------------------------------------------------------------------------
+// per-atom reductions over T fragments (one wavefront per atom, lane (g, x) = lane half, column x of every block)
+// ---------------------------------------------------------------------------------------------
+// M_i = alpha sum_e silu(z2_e), v'_i = v_i + alpha sum_e (wx . silu(z2_e)) rvec_e over the rows e of atom i
+template <int NCB>
+__global__ void __launch_bounds__(256) k_seg_fwd_w(int N, const int32_t* __restrict__ row_ptr, const char* __restrict__ z2_T,
+                                                   const float* __restrict__ rvec, const float* __restrict__ wx, int H,
+                                                   float alpha, const float* __restrict__ v_in, float* __restrict__ M,
+                                                   float* __restrict__ v_out) {
+  const int lane = threadIdx.x & 63, g = lane >> 5, x = lane & 31;
+  const int i = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (i >= N) return;
+  const int e0 = row_ptr[i], e1 = row_ptr[i + 1];
+  float macc[NCB], wxv[NCB];
+#pragma unroll
+  for (int cb = 0; cb < NCB; ++cb) {
+    macc[cb] = 0.f;
+    wxv[cb] = cb * 32 + x < H ? wx[cb * 32 + x] : 0.f;
+  }
+  float s[3] = {0.f, 0.f, 0.f};
+  for (int rb16 = e0 >> 4; rb16 * 16 < e1; ++rb16) {
+    bool ok[8];
+    float rv[8][3];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int r = tset_row(rb16, g, u);
+      ok[u] = r >= e0 && r < e1;
+      const long rr = ok[u] ? r : 0;
+      rv[u][0] = rvec[3 * rr]; rv[u][1] = rvec[3 * rr + 1]; rv[u][2] = rvec[3 * rr + 2];
+    }
+    float y[8] = {};
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb) {
+      float zz[8];
+      unpack8(*reinterpret_cast<const uint4*>(z2_T + (((long)rb16 * NCB + cb) * 64 + lane) * 16), zz);
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const float m = ok[u] ? silu_f(zz[u]) : 0.f;
+        macc[cb] += m;
+        y[u] = fmaf(wxv[cb], m, y[u]);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      s[0] = fmaf(y[u], rv[u][0], s[0]);
+      s[1] = fmaf(y[u], rv[u][1], s[1]);
+      s[2] = fmaf(y[u], rv[u][2], s[2]);
+    }
+  }
+#pragma unroll
+  for (int cb = 0; cb < NCB; ++cb) {
+    const float t = macc[cb] + __shfl_xor(macc[cb], 32);
+    if (g == 0) M[(long)i * (NCB * 32) + cb * 32 + x] = alpha * t;
+  }
+#pragma unroll
+  for (int d = 0; d < 3; ++d) {
+    float t = s[d];
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) t += __shfl_xor(t, o);
+    if (lane == 0) v_out[3 * (long)i + d] = v_in[3 * (long)i + d] + alpha * t;
+  }
+}
+
+// out[i][32 cb + x] = sum over the edges of atom i's list of X[e][32 cb + x]  (X as T fragments).
+// perm == null: the list is the contiguous row range ptr[i] .. ptr[i+1] (whole fragments are read and masked);
+// else the list is perm[ptr[i] .. ptr[i+1]) and the two lane halves take alternate entries, one element at a time.
+template <int NCB>
+__global__ void __launch_bounds__(256) k_segsum_w(int N, const int32_t* __restrict__ ptr, const int32_t* __restrict__ perm,
+                                                  const char* __restrict__ X_T, float* __restrict__ out, long ldo) {
+  const int lane = threadIdx.x & 63, g = lane >> 5, x = lane & 31;
+  const int i = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (i >= N) return;
+  const int e0 = ptr[i], e1 = ptr[i + 1];
+  float acc[NCB];
+#pragma unroll
+  for (int cb = 0; cb < NCB; ++cb) acc[cb] = 0.f;
+  if (perm == nullptr) {
+    for (int rb16 = e0 >> 4; rb16 * 16 < e1; ++rb16) {
+      bool ok[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int r = tset_row(rb16, g, u);
+        ok[u] = r >= e0 && r < e1;
+      }
+#pragma unroll
+      for (int cb = 0; cb < NCB; ++cb) {
+        float zz[8];
+        unpack8(*reinterpret_cast<const uint4*>(X_T + (((long)rb16 * NCB + cb) * 64 + lane) * 16), zz);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc[cb] += ok[u] ? zz[u] : 0.f;
+      }
+    }
+  } else {
+    for (int k = e0 + g; k < e1; k += 2) {
+      const int e = perm[k];
+      const int r = e & 15;
+      const int ge = (r >> 2) & 1, ue = ((r >> 3) << 2) | (r & 3);
+      const unsigned short* base =
+          reinterpret_cast<const unsigned short*>(X_T + ((long)(e >> 4) * NCB * 64 + ge * 32 + x) * 16) + ue;
+#pragma unroll
+      for (int cb = 0; cb < NCB; ++cb) acc[cb] += bf_lo(base[(long)cb * 512]);
+    }
+  }
+#pragma unroll
+  for (int cb = 0; cb < NCB; ++cb) {
+    const float t = acc[cb] + __shfl_xor(acc[cb], 32);
+    if (g == 0) out[(long)i * ldo + cb * 32 + x] = t;
+  }
+}
+
+template <int NCB>
+static int32_t seg_launch(hipStream_t st, bool fwd, int N, const int32_t* ptr, const int32_t* perm, const char* X,
+                          const float* rvec, const float* wx, int H, float alpha, const float* v_in, float* out, long ldo,
+                          float* v_out) {
+  const unsigned grid = (unsigned)((N + 3) / 4);
+  if (fwd) k_seg_fwd_w<NCB><<<grid, 256, 0, st>>>(N, ptr, X, rvec, wx, H, alpha, v_in, out, v_out);
+  else k_segsum_w<NCB><<<grid, 256, 0, st>>>(N, ptr, perm, X, out, ldo);
+  HGNN_LAUNCH_CHECK("wide segment kernel");
+  return HGNN_OK;
+}
+static int32_t launch_seg_w(hipStream_t st, int tag, bool fwd, int Hp, int N, const int32_t* ptr, const int32_t* perm,
+                            const char* X, const float* rvec, const float* wx, int H, float alpha, const float* v_in,
+                            float* out, long ldo, float* v_out) {
+  if (N <= 0) return HGNN_OK;
+  ProfScope ps(tag, st);
+  switch (Hp / 32) {
+    case 12: return seg_launch<12>(st, fwd, N, ptr, perm, X, rvec, wx, H, alpha, v_in, out, ldo, v_out);
+    case 16: return seg_launch<16>(st, fwd, N, ptr, perm, X, rvec, wx, H, alpha, v_in, out, ldo, v_out);
+    case 20: return seg_launch<20>(st, fwd, N, ptr, perm, X, rvec, wx, H, alpha, v_in, out, ldo, v_out);
+    case 24: return seg_launch<24>(st, fwd, N, ptr, perm, X, rvec, wx, H, alpha, v_in, out, ldo, v_out);
+    case 28: return seg_launch<28>(st, fwd, N, ptr, perm, X, rvec, wx, H, alpha, v_in, out, ldo, v_out);
+    case 32: return seg_launch<32>(st, fwd, N, ptr, perm, X, rvec, wx, H, alpha, v_in, out, ldo, v_out);
+  }
+  return set_error(HGNN_ERR_BAD_SHAPE, "padded width %d is not supported", Hp);
+}
+
+// ---------------------------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------------------------
+struct WideDims {
+  int N, H, Hp, Np, ncb, nkb;
+  int64_t E, Ep;
+  WideDims(int N_, int64_t E_, int H_) : N(N_), H(H_), E(E_) {
+    Hp = wide_pad_cols(H);
+    Np = (int)wide_pad_rows(N);
+    Ep = wide_pad_rows(E);
+    ncb = Hp / 32;
+    nkb = Hp / 16;
+  }
+  size_t edge_bytes() const { return (size_t)Ep * Hp * 2; }
+  size_t node_frag_bytes(int parts) const { return (size_t)Np * Hp * 2 * parts; }
+};
+
+struct LayerOffW {
+  long W1, b1, W2, b2, wx, W3, b3, W4, b4, total;
+  explicit LayerOffW(long H) {
+    long o = 0;
+    W1 = o; o += (2 * H + 1) * H;
+    b1 = o; o += H;
+    W2 = o; o += H * H;
+    b2 = o; o += H;
+    wx = o; o += H;
+    W3 = o; o += 2 * H * H;
+    b3 = o; o += H;
+    W4 = o; o += H * H;
+    b4 = o; o += H;
+    total = o;
+  }
+};
+
+struct WideSaved {
+  unsigned short* PQ;   // [Np, 2 Hp] bf16 row-major
+  char* a1_R;           // [Ep, Hp]
+  char* a1_T;
+  char* z2_T;
+  float* M;             // [Np, Hp] fp32 row-major
+  float* z3;            // [Np, Hp]
+  size_t bytes;
+};
+static WideSaved carve_saved_w(void* p, const WideDims& d) {
+  Carver c(p);
+  WideSaved s;
+  s.PQ = c.take<unsigned short>((size_t)d.Np * 2 * d.Hp);
+  s.a1_R = c.take<char>(d.edge_bytes());
+  s.a1_T = c.take<char>(d.edge_bytes());
+  s.z2_T = c.take<char>(d.edge_bytes());
+  s.M = c.take<float>((size_t)d.Np * d.Hp);
+  s.z3 = c.take<float>((size_t)d.Np * d.Hp);
+  s.bytes = c.used();
+  return s;
+}
+
+struct WideWs {
+  unsigned short* packed;   // 6 Hp^2 bf16 (the forward or the transposed set)
+  char* hM_R;               // [Np, 2 Hp] R fragments of [h ; M]
+  char* hM_T;               // the same as T fragments
+  char* x_R;                // [Np, 2 Hp] scratch R operand (a3, g_h', g_z3, g_PQ)
+  char* x_T;                // [Np, 2 Hp] scratch T operand
+  char* a3_T;               // [Np, Hp]
+  float* nodeA;             // [Np, 2 Hp] fp32 (g_a3, then g_hM)
+  unsigned short* gM_b;     // [Np, 2 Hp] bf16 row-major copy of g_hM
+  float* g_PQ;              // [Np, 2 Hp] fp32
+  char* gz2_R;              // [Ep, Hp]
+  char* gz2_T;
+  char* ga1_T;
+  float* cvec;              // [E]
+  float* colpart;           // ELEM_MAX_BLOCKS x 2 x Hp
+  float* cs_partial;        // column sums over atoms
+  float* partial;           // split partials of the weight-gradient products
+  size_t partial_floats;
+  size_t bytes;
+};
+constexpr int WIDE_MAX_SPLITS = 24;
+static WideWs carve_ws_w(void* p, const WideDims& d) {
+  Carver c(p);
+  WideWs w;
+  w.packed = c.take<unsigned short>((size_t)6 * d.Hp * d.Hp);
+  w.hM_R = c.take<char>(d.node_frag_bytes(2));
+  w.hM_T = c.take<char>(d.node_frag_bytes(2));
+  w.x_R = c.take<char>(d.node_frag_bytes(2));
+  w.x_T = c.take<char>(d.node_frag_bytes(2));
+  w.a3_T = c.take<char>(d.node_frag_bytes(1));
+  w.nodeA = c.take<float>((size_t)d.Np * 2 * d.Hp);
+  w.gM_b = c.take<unsigned short>((size_t)d.Np * 2 * d.Hp);
+  w.g_PQ = c.take<float>((size_t)d.Np * 2 * d.Hp);
+  w.gz2_R = c.take<char>(d.edge_bytes());
+  w.gz2_T = c.take<char>(d.edge_bytes());
+  w.ga1_T = c.take<char>(d.edge_bytes());
+  w.cvec = c.take<float>((size_t)d.E + 4);
+  w.colpart = c.take<float>((size_t)ELEM_MAX_BLOCKS * 2 * d.Hp);
+  w.cs_partial = c.take<float>(colsum_rows_partial_floats(d.N, d.Hp));
+  w.partial_floats = (size_t)WIDE_MAX_SPLITS * 2 * d.Hp * d.Hp;
+  w.partial = c.take<float>(w.partial_floats);
+  w.bytes = c.used();
+  return w;
+}
+
+void wide_layer_sizes(int N, int64_t E, int H, size_t* ws_bytes, size_t* saved_bytes) {
+  const WideDims d(N, E, H);
+  *ws_bytes = carve_ws_w(nullptr, d).bytes;
+  *saved_bytes = carve_saved_w(nullptr, d).bytes;
+}
+
+// C = A x W over rows (R fragments of A with a_nkb contraction blocks, packed W with nJ column blocks)
+static FGemmArgs nn_args(const char* A_R, int a_nkb, int nI, const unsigned short* Wp, int nJ, int tag) {
+  FGemmArgs g;
+  g.A = A_R; g.a_si = a_nkb; g.a_sk = 1;
+  g.B = reinterpret_cast<const char*>(Wp); g.b_sj = a_nkb; g.b_sk = 1;
+  g.nI = nI; g.nJ = nJ; g.nkb = a_nkb; g.kper = a_nkb; g.nsplit = 1;
+  g.tag = tag;
+  return g;
+}
+
+// dest = A^T B over `rows` rows (T fragments: A with a_ncb column blocks of which nI from block a_cb0 are used; B alike),
+// split over the rows, partials reduced in order into the caller's [.., H, H] weight-gradient blocks
+static int32_t wgrad_w(hipStream_t st, const WideDims& d, const char* A_T, int a_ncb, int a_cb0, int nI, const char* B_T,
+                       int b_ncb, int b_cb0, int nJ, int64_t rows, float* partial, size_t partial_floats, float* dest,
+                       long strideA, long strideB, int tag) {
+  FGemmArgs g;
+  g.A = A_T + (long)a_cb0 * 1024; g.a_si = 1; g.a_sk = a_ncb;
+  g.B = B_T + (long)b_cb0 * 1024; g.b_sj = 1; g.b_sk = b_ncb;
+  g.nI = nI; g.nJ = nJ;
+  g.nkb = (int)(rows / 16);
+  const long tiles = (long)(nI / 4) * (nJ / 4);
+  long want = (3L * num_cus() + tiles - 1) / tiles;
+  const long cap = (long)(partial_floats / ((size_t)nI * 32 * nJ * 32));
+  if (want > cap) want = cap;
+  if (want > WIDE_MAX_SPLITS) want = WIDE_MAX_SPLITS;
+  if (want < 1) want = 1;
+  int kper = (int)((g.nkb + want - 1) / want);
+  kper = (kper + 1) / 2 * 2;
+  if (kper < 2) kper = 2;
+  g.kper = kper;
+  g.nsplit = g.nkb == 0 ? 1 : (g.nkb + kper - 1) / kper;
+  g.P = partial; g.ldp = (long)nJ * 32; g.split_stride = (long)nI * 32 * nJ * 32;
+  g.tag = tag;
+  HGNN_REQUIRE((size_t)g.nsplit * g.split_stride <= partial_floats, HGNN_ERR_WORKSPACE_TOO_SMALL,
+               "weight-gradient partials do not fit the workspace");
+  HGNN_TRY((launch_fgemm_t<2, 2, EPI_PART>(st, g)));
+  ProfScope ps(tag, st);
+  const long n = g.split_stride;
+  k_reduce_wgrad<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(partial, g.nkb == 0 ? 0 : g.nsplit, g.split_stride, nI * 32,
+                                                              nJ * 32, d.Hp, d.H, dest, strideA, strideB);
+  HGNN_LAUNCH_CHECK("k_reduce_wgrad");
+  return HGNN_OK;
+}
+
+int32_t wide_layer_fwd(hipStream_t st, const WideLayerArgs& a) {
+  const WideDims d(a.N, a.E, a.H);
+  const int H = d.H, Hp = d.Hp;
+  WideWs w = carve_ws_w(a.ws, d);
+  WideSaved s = carve_saved_w(a.saved, d);
+  const LayerOffW o(H);
+  const long HH = (long)H * H, PP = (long)Hp * Hp;
+  const float* W = a.W;
+
+  // packed (elements): [W1a | W1b] at 0 (K = Hp, 2 ncb column blocks), W2 at 2 PP, [W3a ; W3b] at 3 PP (K = 2 Hp), W4 at 5 PP
+  {
+    PackFragArgs pk;
+    pk.src = W; pk.K = H; pk.Nn = H; pk.Hp = Hp;
+    pk.dst = w.packed; pk.nkb_total = d.nkb; pk.nparts = 2;
+    pk.part[0] = {o.W1, H, 1, 0, 0};
+    pk.part[1] = {o.W1 + HH, H, 1, 0, d.ncb};
+    HGNN_TRY(launch_pack_frag(st, pk));
+    pk.dst = w.packed + 2 * PP; pk.nparts = 1;
+    pk.part[0] = {o.W2, H, 1, 0, 0};
+    HGNN_TRY(launch_pack_frag(st, pk));
+    pk.dst = w.packed + 3 * PP; pk.nkb_total = 2 * d.nkb; pk.nparts = 2;
+    pk.part[0] = {o.W3, H, 1, 0, 0};
+    pk.part[1] = {o.W3 + HH, H, 1, d.nkb, 0};
+    HGNN_TRY(launch_pack_frag(st, pk));
+    pk.dst = w.packed + 5 * PP; pk.nkb_total = d.nkb; pk.nparts = 1;
+    pk.part[0] = {o.W4, H, 1, 0, 0};
+    HGNN_TRY(launch_pack_frag(st, pk));
+  }
+  {  // h -> first half of the [h ; M] operand
+    ToFragArgs t;
+    t.X = a.h_in; t.ldx = H; t.M = d.N; t.Mp = d.Np; t.ncol = H; t.Cp = Hp;
+    t.R = w.hM_R; t.r_nkb = 2 * d.nkb; t.r_kb0 = 0;
+    HGNN_TRY(launch_to_frag(st, t));
+  }
+  {  // P | Q = h [W1a | W1b] + [b1 | 0], bf16 row-major for the edge gathers
+    FGemmArgs g = nn_args(w.hM_R, 2 * d.nkb, d.Np / 32, w.packed, 2 * d.ncb, PT_GEMM_NODE);
+    g.nkb = d.nkb; g.kper = d.nkb;            // only the h half of the operand rows
+    g.b_sj = d.nkb;
+    g.M = d.N; g.Cb = s.PQ; g.ldcb = 2 * Hp;
+    g.bias = W + o.b1; g.nbias = H;
+    HGNN_TRY((launch_fgemm_t<4, 2, EPI_ROW>(st, g)));
+  }
+  EdgeElemArgs e;
+  e.E = d.E; e.nrs = d.Ep / 8; e.H = H; e.Hp = Hp;
+  e.dst = a.dst; e.col = a.col; e.d2 = a.d2; e.PQ = s.PQ; e.w1d = W + o.W1 + 2 * HH;
+  e.a1_R = s.a1_R; e.a1_T = s.a1_T;
+  if (d.Ep > 0) {
+    {
+      ProfScope ps(PT_EDGE_FUSED_FWD, st);
+      const long n = e.nrs * (Hp / 8);
+      k_edge_a1<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(e);
+      HGNN_LAUNCH_CHECK("k_edge_a1");
+    }
+    // z2 = a1 W2 + b2 (T fragments)
+    FGemmArgs g = nn_args(s.a1_R, d.nkb, (int)(d.Ep / 32), w.packed + 2 * PP, d.ncb, PT_EDGE_FUSED_FWD);
+    g.T = s.z2_T; g.t_ncb = d.ncb;
+    g.bias = W + o.b2; g.nbias = H;
+    HGNN_TRY((launch_fgemm_t<4, 2, EPI_T>(st, g)));
+  }
+  HGNN_TRY(launch_seg_w(st, PT_SEG_FWD, true, Hp, d.N, a.row_ptr, nullptr, s.z2_T, a.rvec, W + o.wx, H, a.alpha, a.v_in,
+                        s.M, Hp, a.v_out));
+  {  // M -> second half of the [h ; M] operand
+    ToFragArgs t;
+    t.X = s.M; t.ldx = Hp; t.M = d.N; t.Mp = d.Np; t.ncol = Hp; t.Cp = Hp;
+    t.R = w.hM_R; t.r_nkb = 2 * d.nkb; t.r_kb0 = d.nkb;
+    HGNN_TRY(launch_to_frag(st, t));
+  }
+  {  // z3 = [h ; M] W3 + b3
+    FGemmArgs g = nn_args(w.hM_R, 2 * d.nkb, d.Np / 32, w.packed + 3 * PP, d.ncb, PT_GEMM_NODE);
+    g.M = d.N; g.Cf = s.z3; g.ldc = Hp; g.ncol_f = Hp;
+    g.bias = W + o.b3; g.nbias = H;
+    HGNN_TRY((launch_fgemm_t<4, 2, EPI_ROW>(st, g)));
+  }
+  {  // a3 = silu(z3)
+    ToFragArgs t;
+    t.X = s.z3; t.ldx = Hp; t.mode = 1; t.M = d.N; t.Mp = d.Np; t.ncol = H; t.Cp = Hp;
+    t.R = w.x_R; t.r_nkb = d.nkb; t.r_kb0 = 0;
+    HGNN_TRY(launch_to_frag(st, t));
+  }
+  {  // h' = h + a3 W4 + b4
+    FGemmArgs g = nn_args(w.x_R, d.nkb, d.Np / 32, w.packed + 5 * PP, d.ncb, PT_GEMM_NODE);
+    g.M = d.N; g.Cf = a.h_out; g.ldc = H; g.ncol_f = H;
+    g.r1 = a.h_in; g.ld1 = H;
+    g.bias = W + o.b4; g.nbias = H;
+    HGNN_TRY((launch_fgemm_t<4, 2, EPI_ROW>(st, g)));
+  }
+  return HGNN_OK;
+}
+
+int32_t wide_layer_bwd(hipStream_t st, const WideLayerArgs& a) {
+  const WideDims d(a.N, a.E, a.H);
+  const int H = d.H, Hp = d.Hp;
+  WideWs w = carve_ws_w(a.ws, d);
+  WideSaved s = carve_saved_w(a.saved, d);
+  const LayerOffW o(H);
+  const long HH = (long)H * H, PP = (long)Hp * Hp;
+  const float* W = a.W;
+  float* gW = a.gW;
+
+  // packed (elements): W4^T at 0, [W3a^T | W3b^T] at PP (K = Hp, 2 ncb column blocks), W2^T at 3 PP,
+  // [W1a^T ; W1b^T] at 4 PP (K = 2 Hp)
+  {
+    PackFragArgs pk;
+    pk.src = W; pk.K = H; pk.Nn = H; pk.Hp = Hp;
+    pk.dst = w.packed; pk.nkb_total = d.nkb; pk.nparts = 1;
+    pk.part[0] = {o.W4, 1, H, 0, 0};
+    HGNN_TRY(launch_pack_frag(st, pk));
+    pk.dst = w.packed + PP; pk.nparts = 2;
+    pk.part[0] = {o.W3, 1, H, 0, 0};
+    pk.part[1] = {o.W3 + HH, 1, H, 0, d.ncb};
+    HGNN_TRY(launch_pack_frag(st, pk));
+    pk.dst = w.packed + 3 * PP; pk.nparts = 1;
+    pk.part[0] = {o.W2, 1, H, 0, 0};
+    HGNN_TRY(launch_pack_frag(st, pk));
+    pk.dst = w.packed + 4 * PP; pk.nkb_total = 2 * d.nkb; pk.nparts = 2;
+    pk.part[0] = {o.W1, 1, H, 0, 0};
+    pk.part[1] = {o.W1 + HH, 1, H, d.nkb, 0};
+    HGNN_TRY(launch_pack_frag(st, pk));
+  }
+  // operands of the atom-level products
+  {  // [h ; M] as T fragments
+    ToFragArgs t;
+    t.X = a.h_in; t.ldx = H; t.M = d.N; t.Mp = d.Np; t.ncol = H; t.Cp = Hp;
+    t.T = w.hM_T; t.t_ncb = 2 * d.ncb; t.t_cb0 = 0;
+    HGNN_TRY(launch_to_frag(st, t));
+    t.X = s.M; t.ldx = Hp; t.ncol = Hp; t.t_cb0 = d.ncb;
+    HGNN_TRY(launch_to_frag(st, t));
+  }
+  {  // a3 = silu(z3) as T, g_h' as R and T
+    ToFragArgs t;
+    t.X = s.z3; t.ldx = Hp; t.mode = 1; t.M = d.N; t.Mp = d.Np; t.ncol = H; t.Cp = Hp;
+    t.T = w.a3_T; t.t_ncb = d.ncb; t.t_cb0 = 0;
+    HGNN_TRY(launch_to_frag(st, t));
+    ToFragArgs u;
+    u.X = a.g_h_out; u.ldx = H; u.M = d.N; u.Mp = d.Np; u.ncol = H; u.Cp = Hp;
+    u.R = w.x_R; u.r_nkb = d.nkb; u.r_kb0 = 0;
+    u.T = w.x_T; u.t_ncb = d.ncb; u.t_cb0 = 0;
+    HGNN_TRY(launch_to_frag(st, u));
+  }
+  // g_W4 = a3^T g_h', g_b4 = column sums of g_h'
+  HGNN_TRY(wgrad_w(st, d, w.a3_T, d.ncb, 0, d.ncb, w.x_T, d.ncb, 0, d.ncb, d.Np, w.partial, w.partial_floats, gW + o.W4,
+                   0, 0, PT_WGRAD_NODE));
+  HGNN_TRY(launch_colsum_rows(st, a.g_h_out, H, nullptr, 0, 0, d.N, H, Hp, w.cs_partial, gW + o.b4));
+  {  // g_a3 = g_h' W4^T
+    FGemmArgs g = nn_args(w.x_R, d.nkb, d.Np / 32, w.packed, d.ncb, PT_GEMM_NODE);
+    g.M = d.N; g.Cf = w.nodeA; g.ldc = Hp; g.ncol_f = Hp;
+    HGNN_TRY((launch_fgemm_t<4, 2, EPI_ROW>(st, g)));
+  }
+  {  // g_z3 = g_a3 silu'(z3) as R and T; g_b3 = its column sums
+    ToFragArgs t;
+    t.X = w.nodeA; t.ldx = Hp; t.Z = s.z3; t.ldz = Hp; t.mode = 2; t.M = d.N; t.Mp = d.Np; t.ncol = H; t.Cp = Hp;
+    t.R = w.x_R; t.r_nkb = d.nkb; t.r_kb0 = 0;
+    t.T = w.x_T; t.t_ncb = d.ncb; t.t_cb0 = 0;
+    HGNN_TRY(launch_to_frag(st, t));
+    HGNN_TRY(launch_colsum_rows(st, w.nodeA, Hp, s.z3, Hp, 2, d.N, H, Hp, w.cs_partial, gW + o.b3));
+  }
+  // g_W3 = [h ; M]^T g_z3
+  HGNN_TRY(wgrad_w(st, d, w.hM_T, 2 * d.ncb, 0, 2 * d.ncb, w.x_T, d.ncb, 0, d.ncb, d.Np, w.partial, w.partial_floats,
+                   gW + o.W3, HH, 0, PT_WGRAD_NODE));
+  {  // [g_h(a) | g_M] = g_z3 [W3a^T | W3b^T]: fp32 for the residual, bf16 for the edge gathers
+    FGemmArgs g = nn_args(w.x_R, d.nkb, d.Np / 32, w.packed + PP, 2 * d.ncb, PT_GEMM_NODE);
+    g.M = d.N; g.Cf = w.nodeA; g.ldc = 2 * Hp; g.ncol_f = 2 * Hp;
+    g.Cb = w.gM_b; g.ldcb = 2 * Hp;
+    HGNN_TRY((launch_fgemm_t<4, 2, EPI_ROW>(st, g)));
+  }
+  // edge part
+  EdgeElemArgs e;
+  e.E = d.E; e.nrs = d.Ep / 8; e.H = H; e.Hp = Hp;
+  e.dst = a.dst; e.col = a.col; e.d2 = a.d2; e.PQ = s.PQ; e.w1d = W + o.W1 + 2 * HH;
+  e.z2_T = s.z2_T; e.gM = w.gM_b + Hp; e.ldgM = 2 * Hp; e.cvec = w.cvec; e.wx = W + o.wx; e.alpha = a.alpha;
+  e.gz2_R = w.gz2_R; e.gz2_T = w.gz2_T; e.ga1_T = w.ga1_T; e.colpart = w.colpart;
+  const dim3 eb = elem_block(Hp);
+  const int eg = elem_grid(e.nrs, Hp);
+  const size_t esh = (size_t)eb.y * 2 * Hp * sizeof(float);
+  HGNN_TRY(launch_edge_cvec(st, d.E, a.dst, a.rvec, a.g_v_out, a.alpha, w.cvec));
+  {
+    ProfScope ps(PT_EDGE_FUSED_BWD, st);
+    k_edge_gz2<<<eg, eb, esh, st>>>(e);
+    HGNN_LAUNCH_CHECK("k_edge_gz2");
+  }
+  HGNN_TRY(launch_reduce_cols(st, w.colpart, eg, 2 * Hp, H, gW + o.b2));
+  HGNN_TRY(launch_reduce_cols(st, w.colpart + Hp, eg, 2 * Hp, H, gW + o.wx));
+  // g_W2 = a1^T g_z2
+  HGNN_TRY(wgrad_w(st, d, s.a1_T, d.ncb, 0, d.ncb, w.gz2_T, d.ncb, 0, d.ncb, d.Ep, w.partial, w.partial_floats,
+                   gW + o.W2, 0, 0, PT_WGRAD_EDGE));
+  if (d.Ep > 0) {  // g_a1 = g_z2 W2^T (T fragments)
+    FGemmArgs g = nn_args(w.gz2_R, d.nkb, (int)(d.Ep / 32), w.packed + 3 * PP, d.ncb, PT_EDGE_FUSED_BWD);
+    g.T = w.ga1_T; g.t_ncb = d.ncb;
+    HGNN_TRY((launch_fgemm_t<4, 2, EPI_T>(st, g)));
+  }
+  {
+    ProfScope ps(PT_EDGE_FUSED_BWD, st);
+    k_edge_gz1<<<eg, eb, esh, st>>>(e);
+    HGNN_LAUNCH_CHECK("k_edge_gz1");
+  }
+  HGNN_TRY(launch_reduce_cols(st, w.colpart, eg, 2 * Hp, H, gW + o.b1));
+  HGNN_TRY(launch_reduce_cols(st, w.colpart + Hp, eg, 2 * Hp, H, gW + o.W1 + 2 * HH));
+  // g_P, g_Q: per-atom sums of g_z1 over the destination-sorted and the source-sorted lists
+  HGNN_TRY(launch_seg_w(st, PT_SEGSUM_DST, false, Hp, d.N, a.row_ptr, nullptr, w.ga1_T, nullptr, nullptr, H, 0.f, nullptr,
+                        w.g_PQ, 2 * Hp, nullptr));
+  HGNN_TRY(launch_seg_w(st, PT_SEGSUM_SRC, false, Hp, d.N, a.colT_ptr, a.permT, w.ga1_T, nullptr, nullptr, H, 0.f,
+                        nullptr, w.g_PQ + Hp, 2 * Hp, nullptr));
+  {  // [g_P | g_Q] as R (contraction 2 Hp) and T
+    ToFragArgs t;
+    t.X = w.g_PQ; t.ldx = 2 * Hp; t.M = d.N; t.Mp = d.Np; t.ncol = 2 * Hp; t.Cp = 2 * Hp;
+    t.R = w.x_R; t.r_nkb = 2 * d.nkb; t.r_kb0 = 0;
+    t.T = w.x_T; t.t_ncb = 2 * d.ncb; t.t_cb0 = 0;
+    HGNN_TRY(launch_to_frag(st, t));
+  }
+  // g_W1a = h^T g_P, g_W1b = h^T g_Q
+  HGNN_TRY(wgrad_w(st, d, w.hM_T, 2 * d.ncb, 0, d.ncb, w.x_T, 2 * d.ncb, 0, 2 * d.ncb, d.Np, w.partial, w.partial_floats,
+                   gW + o.W1, 0, HH, PT_WGRAD_NODE));
+  {  // g_h = g_h' + g_h(a) + [g_P | g_Q] [W1a^T ; W1b^T]
+    FGemmArgs g = nn_args(w.x_R, 2 * d.nkb, d.Np / 32, w.packed + 4 * PP, d.ncb, PT_GEMM_NODE);
+    g.M = d.N; g.Cf = a.g_h_in; g.ldc = H; g.ncol_f = H;
+    g.r1 = a.g_h_out; g.ld1 = H;
+    g.r2 = w.nodeA; g.ld2 = 2 * Hp;
+    HGNN_TRY((launch_fgemm_t<4, 2, EPI_ROW>(st, g)));
+  }
+  if (a.g_v_in != a.g_v_out) HGNN_TRY(launch_copy_f32(st, a.g_v_out, a.g_v_in, (int64_t)d.N * 3));
+  return HGNN_OK;
+}
+
+}  // namespace hgnn
