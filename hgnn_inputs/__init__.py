@@ -21,6 +21,9 @@ from .weights import (  # noqa: F401
     head_field_slices,
     init_layer_weights,
     init_head_weights,
+    deep_head_field_slices,
+    deep_head_weight_count,
+    init_deep_head_weights,
     init_embedding,
     upstream_grads,
     ZMAX,

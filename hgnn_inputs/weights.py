@@ -6,6 +6,8 @@ Layout of one message-passing layer (float32, matrices row-major [in, out]):
 Layout of one source's decoding branch:
     We1[H,Hh] be1[Hh] We2[Hh] be2[1]   (energy head)   Wf1[H,Hh] bf1[Hh] Wf2[Hh] bf2[1]   (force head)
 All S branches are stored back to back.
+Deep branch (D hidden layers per head; the paper's heads have three layers, 889 units wide): the energy head
+then the force head, each  W1[H,Hh] b1[Hh]  Wl[Hh,Hh] bl[Hh] (l = 2..D)  wo[Hh] bo[1];  D = 1 is the layout above.
 """
 from __future__ import annotations
 
@@ -74,6 +76,39 @@ def init_head_weights(rng, H, Hh, S, bias_scale=0.1):
     fan = {"We1": H, "We2": Hh, "Wf1": H, "Wf2": Hh}
     return np.concatenate([_fill(rng, _head_shapes(H, Hh), HEAD_FIELDS, fan, bias_scale)
                            for _ in range(S)])
+
+
+def deep_head_field_slices(H, Hh, D):
+    """name -> (lo, hi, shape) inside one branch; names are "e.W1", "e.b1", ..., "e.wo", "e.bo", "f.W1", ..."""
+    shapes, order = {}, []
+    for which in ("e", "f"):
+        shapes[f"{which}.W1"], shapes[f"{which}.b1"] = (H, Hh), (Hh,)
+        order += [f"{which}.W1", f"{which}.b1"]
+        for l in range(2, D + 1):
+            shapes[f"{which}.W{l}"], shapes[f"{which}.b{l}"] = (Hh, Hh), (Hh,)
+            order += [f"{which}.W{l}", f"{which}.b{l}"]
+        shapes[f"{which}.wo"], shapes[f"{which}.bo"] = (Hh,), (1,)
+        order += [f"{which}.wo", f"{which}.bo"]
+    return _slices(shapes, order)[0]
+
+
+def deep_head_weight_count(H, Hh, D):
+    return 2 * (H * Hh + Hh + (D - 1) * (Hh * Hh + Hh) + Hh + 1)
+
+
+def init_deep_head_weights(rng, H, Hh, D, S, bias_scale=0.1):
+    sl = deep_head_field_slices(H, Hh, D)
+    out = np.empty(S * deep_head_weight_count(H, Hh, D), dtype=np.float32)
+    per = deep_head_weight_count(H, Hh, D)
+    for s in range(S):
+        for name, (lo, hi, shp) in sl.items():
+            field = name.split(".")[1]
+            if field[0] in "Ww":
+                b = 1.0 / np.sqrt(shp[0])
+                out[s * per + lo:s * per + hi] = rng.uniform(-b, b, size=hi - lo)
+            else:
+                out[s * per + lo:s * per + hi] = rng.uniform(-bias_scale, bias_scale, size=hi - lo)
+    return out
 
 
 def init_embedding(rng, H):

@@ -166,8 +166,8 @@ int32_t hgnn_pool_by_graph_bwd(void* stream, int32_t N, int32_t G, int32_t H, in
 
 /* ---------------------------------------------------------------------------------------------
  * Two-level multi-task decoder, all S branches resident on this GPU. Graph g is decoded by branch
- * s = source_id[g] and by no other ("the forward propagation of an MTL output head does not
- * require coordination with the other output heads"):
+ * s = source_id[g] and by no other (the heads of different sources never exchange anything in the
+ * forward pass: paper, section "Multi-task parallelism"):
  *   e_g = We2_s . silu(We1_s^T p_g + be1_s) + be2_s                       (energy per atom)
  *   q_i = Wf2_s . silu(Wf1_s^T h_i + bf1_s) + bf2_s ,  F_i = q_i * v_i     (atomic force)
  * Whead: S branches back to back, each  We1[H,Hh] be1[Hh] We2[Hh] be2[1] Wf1[H,Hh] bf1[Hh] Wf2[Hh]

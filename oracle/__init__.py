@@ -31,5 +31,9 @@ from .model import (  # noqa: F401
     routing_plan,
     heads_fwd,
     heads_bwd,
+    deep_head_shapes,
+    unpack_deep_heads,
+    heads_deep_fwd,
+    heads_deep_bwd,
     step_fwd_bwd,
 )

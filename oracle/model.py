@@ -269,12 +269,118 @@ def heads_bwd(cache, g_energy, g_force):
 
 
 # ---------------------------------------------------------------------------------------------
+# heads with D fully connected hidden layers (in the paper's model every dataset-specific head has
+# three of them, 889 units wide: section "Numerical Results")
+# ---------------------------------------------------------------------------------------------
+def deep_head_shapes(H, Hh, D):
+    """Ordered (name, shape) list of one head: W1[H,Hh] b1[Hh], then Wl[Hh,Hh] bl[Hh] for l = 2..D,
+    then the output layer wo[Hh] bo[1]. D = 1 is the layout of unpack_heads."""
+    out = [("W1", (H, Hh)), ("b1", (Hh,))]
+    for l in range(2, D + 1):
+        out += [(f"W{l}", (Hh, Hh)), (f"b{l}", (Hh,))]
+    out += [("wo", (Hh,)), ("bo", (1,))]
+    return out
+
+
+def unpack_deep_heads(flat, H, Hh, D, S):
+    """List of S branches; a branch is {"e": head, "f": head}, a head maps field name -> array.
+    Storage: branch after branch, in a branch the energy head then the force head."""
+    shapes = deep_head_shapes(H, Hh, D)
+    per_head = sum(int(np.prod(s)) for _, s in shapes)
+    assert len(flat) == 2 * per_head * S, "head buffer has the wrong length"
+    out, o = [], 0
+    for _ in range(S):
+        br = {}
+        for which in ("e", "f"):
+            d = {}
+            for k, shp in shapes:
+                n = int(np.prod(shp))
+                d[k] = np.asarray(flat[o:o + n], dtype=np.float64).reshape(shp)
+                o += n
+            br[which] = d
+        out.append(br)
+    return out
+
+
+def _mlp_fwd(x, w, D):
+    """x [rows, in] through D hidden layers (silu after each) and the scalar output layer."""
+    zs, acts = [], [x]
+    for l in range(1, D + 1):
+        z = acts[-1] @ w[f"W{l}"] + w[f"b{l}"]
+        zs.append(z)
+        acts.append(silu(z))
+    return acts[-1] @ w["wo"] + w["bo"][0], zs, acts
+
+
+def _mlp_bwd(g_out, w, gw, zs, acts, D):
+    """Reverse of _mlp_fwd for upstream g_out [rows]; adds into gw, returns the gradient of x."""
+    gw["bo"][0] += g_out.sum()
+    gw["wo"] += acts[D].T @ g_out
+    g_a = g_out[:, None] * w["wo"][None, :]
+    for l in range(D, 0, -1):
+        g_z = g_a * dsilu(zs[l - 1])
+        gw[f"b{l}"] += g_z.sum(axis=0)
+        gw[f"W{l}"] += acts[l - 1].T @ g_z
+        g_a = g_z @ w[f"W{l}"].T
+    return g_a
+
+
+def heads_deep_fwd(p, h, v, graph_off, source_id, Whead_flat, Hh, D, S):
+    """Like heads_fwd with D hidden layers per head: e_g = MLP_e,s(p_g), q_i = MLP_f,s(h_i), F_i = q_i v_i."""
+    p = np.asarray(p, dtype=np.float64)
+    h = np.asarray(h, dtype=np.float64)
+    v = np.asarray(v, dtype=np.float64)
+    G, H = p.shape
+    N = h.shape[0]
+    heads = unpack_deep_heads(Whead_flat, H, Hh, D, S)
+    energy = np.zeros(G, dtype=np.float64)
+    q = np.zeros(N, dtype=np.float64)
+    per_graph = []
+    for g in range(G):
+        w = heads[int(source_id[g])]
+        lo, hi = int(graph_off[g]), int(graph_off[g + 1])
+        e, ze, ae = _mlp_fwd(p[g:g + 1], w["e"], D)
+        energy[g] = e[0]
+        qq, zf, af = _mlp_fwd(h[lo:hi], w["f"], D)
+        q[lo:hi] = qq
+        per_graph.append((ze, ae, zf, af))
+    force = q[:, None] * v
+    cache = dict(p=p, h=h, v=v, graph_off=np.asarray(graph_off), source_id=np.asarray(source_id), heads=heads,
+                 per_graph=per_graph, q=q, Hh=Hh, D=D, S=S)
+    return energy, force, cache
+
+
+def heads_deep_bwd(cache, g_energy, g_force):
+    """Returns (g_p [G,H], g_h [N,H], g_v [N,3], flat head-weight gradient in the layout of the weights)."""
+    c = cache
+    p, h, v, D = c["p"], c["h"], c["v"], c["D"]
+    g_energy = np.asarray(g_energy, dtype=np.float64)
+    g_force = np.asarray(g_force, dtype=np.float64)
+    gheads = [{wh: {k: np.zeros_like(a) for k, a in br[wh].items()} for wh in ("e", "f")} for br in c["heads"]]
+    g_p = np.zeros_like(p)
+    g_h = np.zeros_like(h)
+    g_q = np.einsum("nc,nc->n", g_force, v)
+    g_v = c["q"][:, None] * g_force
+    for g in range(p.shape[0]):
+        s = int(c["source_id"][g])
+        lo, hi = int(c["graph_off"][g]), int(c["graph_off"][g + 1])
+        ze, ae, zf, af = c["per_graph"][g]
+        g_p[g] = _mlp_bwd(g_energy[g:g + 1], c["heads"][s]["e"], gheads[s]["e"], ze, ae, D)[0]
+        g_h[lo:hi] = _mlp_bwd(g_q[lo:hi], c["heads"][s]["f"], gheads[s]["f"], zf, af, D)
+    H, Hh = p.shape[1], c["Hh"]
+    order = [k for k, _ in deep_head_shapes(H, Hh, D)]
+    flat = np.concatenate([gheads[s][wh][k].ravel() for s in range(c["S"]) for wh in ("e", "f") for k in order])
+    return g_p, g_h, g_v, flat
+
+
+# ---------------------------------------------------------------------------------------------
 # whole step
 # ---------------------------------------------------------------------------------------------
 def step_fwd_bwd(Z, graph_off, source_id, graph, emb, layer_weights, head_weights, Hh, S, alpha,
-                 g_energy=None, g_force=None, keep_layers=False):
+                 g_energy=None, g_force=None, keep_layers=False, D=None):
     """Embedding -> L layers -> mean pool -> heads, then (if upstream gradients are given) the
-    whole reverse pass. `graph` is the dict returned by oracle.radius_graph."""
+    whole reverse pass. `graph` is the dict returned by oracle.radius_graph. D: hidden layers per
+    head (None: the one-hidden-layer heads of heads_fwd)."""
     H = emb.shape[1]
     N = len(Z)
     dst, col, d2, rvec = graph["dst"], graph["col"], graph["d2"], graph["rvec"]
@@ -287,11 +393,18 @@ def step_fwd_bwd(Z, graph_off, source_id, graph, emb, layer_weights, head_weight
         if keep_layers:
             hs.append(h)
     p = pool_fwd(h, graph_off)
-    energy, force, hc = heads_fwd(p, h, v, graph_off, source_id, head_weights, Hh, S)
+    if D is None:
+        energy, force, hc = heads_fwd(p, h, v, graph_off, source_id, head_weights, Hh, S)
+    else:
+        energy, force, hc = heads_deep_fwd(p, h, v, graph_off, source_id, head_weights, Hh, D, S)
     out = dict(h=h, v=v, p=p, energy=energy, force=force, hs=hs)
     if g_energy is None:
         return out
-    g_p, g_h, g_v, gheads = heads_bwd(hc, g_energy, g_force)
+    if D is None:
+        g_p, g_h, g_v, gheads = heads_bwd(hc, g_energy, g_force)
+        g_heads = np.concatenate([pack_fields(d, _HEAD_FIELDS) for d in gheads])
+    else:
+        g_p, g_h, g_v, g_heads = heads_deep_bwd(hc, g_energy, g_force)
     g_h = g_h + pool_bwd(g_p, graph_off, N)
     g_layers = []
     for c in reversed(caches):
@@ -300,7 +413,7 @@ def step_fwd_bwd(Z, graph_off, source_id, graph, emb, layer_weights, head_weight
     g_layers.reverse()
     out.update(
         g_emb=embed_bwd(Z, g_h, emb.shape[0]), g_layers=g_layers,
-        g_heads=np.concatenate([pack_fields(d, _HEAD_FIELDS) for d in gheads]),
+        g_heads=g_heads,
         g_h0=g_h, g_v0=g_v,
     )
     return out

@@ -498,3 +498,117 @@ def test_isolated_atom_keeps_v_and_gets_zero_aggregate():
     _, v, c = oracle.mp_layer_fwd(h0, np.ones((3, 3)), P["g"]["dst"], P["g"]["col"], P["g"]["d2"],
                                   P["g"]["rvec"], P["Ws"][0], 1.0)
     assert np.all(c["M"][2] == 0.0) and np.all(v[2] == 1.0) and np.any(c["M"][0] != 0.0)
+
+
+# ---------------------------------------------------------------------------------------------
+# heads with D hidden layers
+# ---------------------------------------------------------------------------------------------
+def _deep_problem(seed, H, Hh, D, S):
+    from hgnn_inputs import init_deep_head_weights
+    b = small_mixed_batch(seed, S=S)
+    rng = np.random.default_rng(seed + 500)
+    h = rng.standard_normal((b.N, H))
+    v = rng.standard_normal((b.N, 3))
+    p = oracle.pool_fwd(h, b.graph_off)
+    Wh = init_deep_head_weights(rng, H, Hh, D, S).astype(np.float64)
+    gE, gF = upstream_grads(rng, b.G, b.N)
+    return b, h, v, p, Wh, gE.astype(np.float64), gF.astype(np.float64)
+
+
+def test_deep_heads_with_one_hidden_layer_are_the_plain_heads():
+    """D = 1 has the plain heads' buffer layout and must give their numbers (those are pinned by scalar loops)."""
+    H, Hh, S = 7, 5, 3
+    b, h, v, p, Wh, gE, gF = _deep_problem(31, H, Hh, 1, S)
+    assert len(Wh) == S * head_weight_count(H, Hh)
+    e1, f1, c1 = oracle.heads_fwd(p, h, v, b.graph_off, b.source_id, Wh, Hh, S)
+    e2, f2, c2 = oracle.heads_deep_fwd(p, h, v, b.graph_off, b.source_id, Wh, Hh, 1, S)
+    assert np.allclose(e1, e2, rtol=1e-13, atol=1e-13) and np.allclose(f1, f2, rtol=1e-13, atol=1e-13)
+    gp1, gh1, gv1, gheads = oracle.heads_bwd(c1, gE, gF)
+    flat1 = np.concatenate([np.concatenate([np.ravel(d[k]) for k in ("We1", "be1", "We2", "be2", "Wf1", "bf1", "Wf2", "bf2")])
+                            for d in gheads])
+    gp2, gh2, gv2, flat2 = oracle.heads_deep_bwd(c2, gE, gF)
+    for x, y in ((gp1, gp2), (gh1, gh2), (gv1, gv2), (flat1, flat2)):
+        assert np.allclose(x, y, rtol=1e-12, atol=1e-13)
+
+
+def test_deep_heads_forward_by_scalar_loops():
+    """Three hidden layers evaluated value by value, reading the flat buffer by explicit index."""
+    from hgnn_inputs import deep_head_field_slices, deep_head_weight_count
+    H, Hh, D, S = 4, 3, 3, 2
+    b, h, v, p, Wh, _, _ = _deep_problem(32, H, Hh, D, S)
+    energy, force, _ = oracle.heads_deep_fwd(p, h, v, b.graph_off, b.source_id, Wh, Hh, D, S)
+    sl = deep_head_field_slices(H, Hh, D)
+    per = deep_head_weight_count(H, Hh, D)
+
+    def mlp(x, base, which):
+        a = [float(t) for t in x]
+        for l in range(1, D + 1):
+            nin = H if l == 1 else Hh
+            oW, ob = sl[f"{which}.W{l}"][0], sl[f"{which}.b{l}"][0]
+            a = [_silu(float(Wh[base + ob + n]) + sum(a[k] * Wh[base + oW + k * Hh + n] for k in range(nin)))
+                 for n in range(Hh)]
+        return float(Wh[base + sl[f"{which}.bo"][0]]) + sum(a[n] * Wh[base + sl[f"{which}.wo"][0] + n] for n in range(Hh))
+
+    for g in range(b.G):
+        base = int(b.source_id[g]) * per
+        assert abs(mlp(p[g], base, "e") - energy[g]) <= 1e-12 * max(1.0, abs(energy[g]))
+        for i in range(int(b.graph_off[g]), int(b.graph_off[g + 1])):
+            q = mlp(h[i], base, "f")
+            assert np.allclose(q * v[i], force[i], rtol=1e-12, atol=1e-13)
+
+
+def test_deep_heads_backward_equals_torch_autograd():
+    from hgnn_inputs import deep_head_field_slices, deep_head_weight_count
+    H, Hh, D, S = 6, 5, 3, 3
+    b, h, v, p, Wh, gE, gF = _deep_problem(33, H, Hh, D, S)
+    _, _, c = oracle.heads_deep_fwd(p, h, v, b.graph_off, b.source_id, Wh, Hh, D, S)
+    g_p, g_h, g_v, g_W = oracle.heads_deep_bwd(c, gE, gF)
+    sl = deep_head_field_slices(H, Hh, D)
+    per = deep_head_weight_count(H, Hh, D)
+    tp, th, tv, tW = (torch.tensor(x, requires_grad=True) for x in (p, h, v, Wh))
+    silu = torch.nn.functional.silu
+    loss = torch.zeros((), dtype=torch.float64)
+    for g in range(b.G):
+        s = int(b.source_id[g])
+        lo, hi = int(b.graph_off[g]), int(b.graph_off[g + 1])
+        f = {k: tW[s * per + a:s * per + e].reshape(shp) for k, (a, e, shp) in sl.items()}
+        xe, xf = tp[g:g + 1], th[lo:hi]
+        for l in range(1, D + 1):
+            xe = silu(xe @ f[f"e.W{l}"] + f[f"e.b{l}"])
+            xf = silu(xf @ f[f"f.W{l}"] + f[f"f.b{l}"])
+        e = xe @ f["e.wo"] + f["e.bo"][0]
+        q = xf @ f["f.wo"] + f["f.bo"][0]
+        loss = loss + torch.as_tensor(gE[g]) * e[0] + torch.sum(torch.as_tensor(gF[lo:hi]) * (q[:, None] * tv[lo:hi]))
+    loss.backward()
+    for mine, ref in ((g_p, tp.grad), (g_h, th.grad), (g_v, tv.grad), (g_W, tW.grad)):
+        ref = ref.numpy()
+        assert np.max(np.abs(mine - ref)) <= 1e-10 * max(1.0, np.max(np.abs(ref)))
+
+
+def test_whole_step_with_deep_heads_by_finite_differences():
+    from hgnn_inputs import init_deep_head_weights
+    P = make_problem(seed=34, H=6, Hh=5, L=2, S=3)
+    D = 3
+    rng = np.random.default_rng(7)
+    Wh = init_deep_head_weights(rng, P["H"], P["Hh"], D, P["S"]).astype(np.float64)
+    b = P["b"]
+
+    def step(emb, Ws, Wh_, grads):
+        return oracle.step_fwd_bwd(b.Z, b.graph_off, b.source_id, P["g"], emb, Ws, Wh_, P["Hh"], P["S"], P["alpha"],
+                                   P["gE"] if grads else None, P["gF"] if grads else None, D=D)
+
+    out = step(P["emb"], P["Ws"], Wh, True)
+    d_emb = rng.standard_normal(P["emb"].shape)
+    d_Ws = [rng.standard_normal(w.shape) for w in P["Ws"]]
+    d_Wh = rng.standard_normal(Wh.shape)
+    ana = (np.sum(out["g_emb"] * d_emb) + sum(np.sum(g * d) for g, d in zip(out["g_layers"], d_Ws))
+           + np.sum(out["g_heads"] * d_Wh))
+    eps = 1e-6
+
+    def loss(sign):
+        o = step(P["emb"] + sign * eps * d_emb, [w + sign * eps * d for w, d in zip(P["Ws"], d_Ws)],
+                 Wh + sign * eps * d_Wh, False)
+        return float(np.sum(P["gE"] * o["energy"]) + np.sum(P["gF"] * o["force"]))
+
+    num = (loss(+1) - loss(-1)) / (2 * eps)
+    assert abs(num - ana) <= 1e-6 * max(1.0, abs(ana)), (num, ana)
