@@ -122,7 +122,10 @@ int32_t hgnn_embed_bwd(void* stream, int32_t N, int32_t H, const int32_t* Z,
  * _bwd takes g_h_out = dL/dh', g_v_out = dL/dv' and writes g_h_in = dL/dh, g_v_in = dL/dv and gW.
  * d2 and rvec are constants of the step (no gradient with respect to positions).
  * h_out may not alias h_in; g_h_in may not alias g_h_out.
- * Errors: BAD_SHAPE for H outside {64,128,256} or an unknown dtype; OVERFLOW if E > 2^31 - 129 or
+ * H is 64, 128 or 256 (either dtype), or any width in 257..1024 with dtype HGNN_BF16 (the paper's backbone has 866
+ * hidden units, section "Numerical Results"; such widths are padded to a multiple of 128 inside the library and
+ * float32 operands are UNIMPLEMENTED for them).
+ * Errors: BAD_SHAPE for any other H or an unknown dtype; OVERFLOW if E > 2^31 - 129 or
  * N * 2H * 4 bytes reaches 4 GiB (the edge kernels index edges and gathered rows with 32 bits);
  * WORKSPACE_TOO_SMALL if ws / saved are smaller than the query says; UNIMPLEMENTED if saved == NULL.
  * _bwd also enqueues weight-gradient work on a stream the library creates once (default priority). It
@@ -202,6 +205,35 @@ int32_t hgnn_multihead_decode_bwd(void* stream, int32_t N, int32_t G, int32_t H,
                                   float* g_p /*out [G,H]*/, float* g_h /*out [N,H]*/,
                                   float* g_v /*out [N,3]*/, float* gWhead /*out*/,
                                   void* ws, size_t ws_bytes);
+
+/* ---------------------------------------------------------------------------------------------
+ * The same decoder with D fully connected hidden layers per head (paper, section "Numerical Results": every
+ * dataset-specific head has three layers of 889 units), silu after each hidden layer:
+ *   a_0 = p_g (energy head) or h_i (force head);  a_l = silu(W_l^T a_{l-1} + b_l), l = 1..D;  out = wo . a_D + bo
+ *   e_g = out of the energy head,  F_i = (out of the force head) * v_i
+ * Whead: S branches back to back, each the energy head then the force head, a head being
+ *   W_1[H,Hh] b_1[Hh]  W_l[Hh,Hh] b_l[Hh] (l = 2..D)  wo[Hh] bo[1]
+ * (D = 1 is the layout of hgnn_multihead_decode_*). gWhead has the same layout; a branch with no graph in the
+ * batch gets exactly zero. plan, p, h, v, energy, force, saved, ws and the gradients are as for
+ * hgnn_multihead_decode_*. 1 <= H, Hh <= 1024 (any value), 1 <= D <= 8, 1 <= S <= 1024; dtype must be HGNN_BF16
+ * (HGNN_F32 -> UNIMPLEMENTED). Errors otherwise as for hgnn_multihead_decode_*. Only enqueues work.
+ * ------------------------------------------------------------------------------------------- */
+int32_t hgnn_multihead_deep_workspace_bytes(int32_t N, int32_t G, int32_t H, int32_t Hh, int32_t D, int32_t S,
+                                            int32_t dtype, size_t* ws_bytes_host, size_t* saved_bytes_host);
+
+int32_t hgnn_multihead_deep_fwd(void* stream, int32_t N, int32_t G, int32_t H, int32_t Hh, int32_t D, int32_t S,
+                                int32_t dtype, const int32_t* plan,
+                                const float* p /*[G,H]*/, const float* h /*[N,H]*/, const float* v /*[N,3]*/,
+                                const float* Whead, float* energy /*out [G]*/, float* force /*out [N,3]*/,
+                                void* saved, size_t saved_bytes, void* ws, size_t ws_bytes);
+
+int32_t hgnn_multihead_deep_bwd(void* stream, int32_t N, int32_t G, int32_t H, int32_t Hh, int32_t D, int32_t S,
+                                int32_t dtype, const int32_t* plan,
+                                const float* p, const float* h, const float* v, const float* Whead,
+                                const void* saved, size_t saved_bytes,
+                                const float* g_energy /*[G]*/, const float* g_force /*[N,3]*/,
+                                float* g_p /*out [G,H]*/, float* g_h /*out [N,H]*/, float* g_v /*out [N,3]*/,
+                                float* gWhead /*out*/, void* ws, size_t ws_bytes);
 
 /* ---------------------------------------------------------------------------------------------
  * AdamW update of a flat float32 parameter buffer (paper, training setup: "AdamW" with learning rate 0.001;

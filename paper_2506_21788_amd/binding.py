@@ -24,6 +24,7 @@ EXPORTS = [
     "hgnn_pool_by_graph_fwd", "hgnn_pool_by_graph_bwd",
     "hgnn_multihead_plan_ints", "hgnn_multihead_plan",
     "hgnn_multihead_decode_workspace_bytes", "hgnn_multihead_decode_fwd", "hgnn_multihead_decode_bwd",
+    "hgnn_multihead_deep_workspace_bytes", "hgnn_multihead_deep_fwd", "hgnn_multihead_deep_bwd",
     "hgnn_adamw_step", "hgnn_mfma_probe",
     "hgnn_profile_begin", "hgnn_profile_end", "hgnn_profile_num_tags", "hgnn_profile_tag_name",
     "hgnn_profile_read",
@@ -81,6 +82,11 @@ _dec_fwd = _sig("hgnn_multihead_decode_fwd", vp, i32, i32, i32, i32, i32, i32, v
                 vp, sz, vp, sz)
 _dec_bwd = _sig("hgnn_multihead_decode_bwd", vp, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, sz,
                 vp, vp, vp, vp, vp, vp, vp, sz)
+_deep_ws = _sig("hgnn_multihead_deep_workspace_bytes", i32, i32, i32, i32, i32, i32, i32, C.POINTER(sz), C.POINTER(sz))
+_deep_fwd = _sig("hgnn_multihead_deep_fwd", vp, i32, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp,
+                 vp, sz, vp, sz)
+_deep_bwd = _sig("hgnn_multihead_deep_bwd", vp, i32, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, sz,
+                 vp, vp, vp, vp, vp, vp, vp, sz)
 
 
 def last_error_string() -> str:
@@ -213,6 +219,24 @@ def multihead_decode_bwd(N, G, H, Hh, S, dtype, plan, p, h, v, Whead, saved, g_e
     _check(_dec_bwd(_stream(), N, G, H, Hh, S, dtype, _p(plan), _p(p), _p(h), _p(v), _p(Whead), _p(saved),
                     _nbytes(saved), _p(g_energy), _p(g_force), _p(g_p), _p(g_h), _p(g_v), _p(gWhead), _p(ws),
                     _nbytes(ws)))
+
+
+def multihead_deep_workspace_bytes(N, G, H, Hh, D, S, dtype):
+    a, b = sz(0), sz(0)
+    _check(_deep_ws(N, G, H, Hh, D, S, dtype, C.byref(a), C.byref(b)))
+    return a.value, b.value
+
+
+def multihead_deep_fwd(N, G, H, Hh, D, S, dtype, plan, p, h, v, Whead, energy, force, saved, ws):
+    _check(_deep_fwd(_stream(), N, G, H, Hh, D, S, dtype, _p(plan), _p(p), _p(h), _p(v), _p(Whead), _p(energy),
+                     _p(force), _p(saved), _nbytes(saved), _p(ws), _nbytes(ws)))
+
+
+def multihead_deep_bwd(N, G, H, Hh, D, S, dtype, plan, p, h, v, Whead, saved, g_energy, g_force, g_p, g_h, g_v,
+                       gWhead, ws):
+    _check(_deep_bwd(_stream(), N, G, H, Hh, D, S, dtype, _p(plan), _p(p), _p(h), _p(v), _p(Whead), _p(saved),
+                     _nbytes(saved), _p(g_energy), _p(g_force), _p(g_p), _p(g_h), _p(g_v), _p(gWhead), _p(ws),
+                     _nbytes(ws)))
 
 
 # ------------------------------------------------------------------------------------------------

@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libhgnn.so")
-SOURCES = ["neighbor.hip", "gemm.hip", "edge.hip", "edge_fused.hip", "layer.hip", "wide.hip", "heads.hip", "optim.hip", "prof.hip"]
+SOURCES = ["neighbor.hip", "gemm.hip", "edge.hip", "edge_fused.hip", "layer.hip", "wide.hip", "heads.hip", "heads_deep.hip", "optim.hip", "prof.hip"]
 
 COMMON = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",

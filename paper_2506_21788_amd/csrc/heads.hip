@@ -3,6 +3,7 @@
 #include "devmath.h"
 #include "edgeops.h"
 #include "gemm.h"
+#include "plan.h"
 
 namespace hgnn {
 
@@ -129,30 +130,66 @@ __global__ void k_pool_bwd(int N, int G, int H, int mode, const int32_t* __restr
 }
 
 // ---------------------------------------------------------------------------------------------
-// routing plan
+// the same four operations for any other width (one element per thread; same summation orders as above would need
+// the same chunking, so these are used only where the vector forms do not apply: H outside {64, 128, 256})
 // ---------------------------------------------------------------------------------------------
-struct PlanView {
-  int32_t *grp_graph_ptr, *graph_perm, *grp_atom_ptr, *atom_perm, *atom_graph, *graph_src, *graph_dst_off, *status;
-  int64_t ints;
-};
+inline bool any_H(int H) { return H >= 1 && H <= 1024; }
 
-template <typename T>
-static PlanView plan_view(T* plan, int N, int G, int S) {
-  PlanView v;
-  int32_t* p = const_cast<int32_t*>(plan);
-  int64_t o = 0;
-  v.grp_graph_ptr = p + o; o += S + 1;
-  v.graph_perm = p + o; o += G;
-  v.grp_atom_ptr = p + o; o += S + 1;
-  v.atom_perm = p + o; o += N;
-  v.atom_graph = p + o; o += N;
-  v.graph_src = p + o; o += G;
-  v.graph_dst_off = p + o; o += G;
-  v.status = p + o; o += 4;
-  v.ints = o;
-  return v;
+__global__ void k_embed_fwd_any(int N, int H, const int32_t* __restrict__ Z, const float* __restrict__ emb,
+                                float* __restrict__ h) {
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (int64_t)N * H) return;
+  const int64_t i = idx / H;
+  const int c = (int)(idx - i * H);
+  int z = Z[i];
+  z = z < 0 ? 0 : (z > HGNN_ZMAX ? HGNN_ZMAX : z);
+  h[idx] = emb[(long)z * H + c];
 }
 
+// block (z, chunk), thread = column (strided): atoms of the chunk with Z == z in ascending order
+__global__ void __launch_bounds__(256)
+k_embed_bwd_part_any(int N, int H, const int32_t* __restrict__ Z, const float* __restrict__ g_h,
+                     float* __restrict__ part /*[nchunk][ZMAX+1][H]*/) {
+  const int z = blockIdx.x, chunk = blockIdx.y;
+  const int lo = chunk * EMB_CHUNK;
+  const int hi = lo + EMB_CHUNK < N ? lo + EMB_CHUNK : N;
+  for (int c = threadIdx.x; c < H; c += 256) {
+    float acc = 0.f;
+    for (int i = lo; i < hi; ++i)
+      if (Z[i] == z) acc += g_h[(size_t)i * H + c];
+    part[((size_t)chunk * (HGNN_ZMAX + 1) + z) * H + c] = acc;
+  }
+}
+
+__global__ void __launch_bounds__(256)
+k_pool_fwd_any(int H, int mode, const int32_t* __restrict__ graph_off, const float* __restrict__ h, float* __restrict__ p) {
+  const int g = blockIdx.x;
+  const int lo = graph_off[g], hi = graph_off[g + 1];
+  const float sc = (mode == HGNN_POOL_MEAN && hi > lo) ? 1.0f / (float)(hi - lo) : 1.0f;
+  for (int c = threadIdx.x; c < H; c += 256) {
+    float acc = 0.f;
+    for (int i = lo; i < hi; ++i) acc += h[(size_t)i * H + c];
+    p[(size_t)g * H + c] = acc * sc;
+  }
+}
+
+__global__ void k_pool_bwd_any(int N, int G, int H, int mode, const int32_t* __restrict__ graph_off,
+                               const float* __restrict__ g_p, float* __restrict__ g_h, int accumulate) {
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (int64_t)N * H) return;
+  const int i = (int)(idx / H);
+  const int c = (int)(idx - (int64_t)i * H);
+  const int g = find_graph_of_atom(graph_off, G, i);
+  const int n = graph_off[g + 1] - graph_off[g];
+  const float sc = (mode == HGNN_POOL_MEAN) ? 1.0f / (float)n : 1.0f;
+  float v = g_p[(size_t)g * H + c] * sc;
+  if (accumulate) v += g_h[idx];
+  g_h[idx] = v;
+}
+
+// ---------------------------------------------------------------------------------------------
+// routing plan
+// ---------------------------------------------------------------------------------------------
 // one block; thread s collects the graphs of source s in ascending order (stable by construction)
 __global__ void k_plan_graphs(int G, int S, const int32_t* __restrict__ graph_off, const int32_t* __restrict__ source_id,
                               PlanView v) {
@@ -367,17 +404,18 @@ using namespace hgnn;
 
 extern "C" int32_t hgnn_embed_fwd(void* stream, int32_t N, int32_t H, const int32_t* Z, const float* emb, float* h) {
   hipStream_t st = static_cast<hipStream_t>(stream);
-  HGNN_REQUIRE(N >= 0 && valid_H(H), HGNN_ERR_BAD_SHAPE, "embed_fwd: bad N or H");
+  HGNN_REQUIRE(N >= 0 && any_H(H), HGNN_ERR_BAD_SHAPE, "embed_fwd: bad N or H");
   if (N == 0) return HGNN_OK;
   HGNN_REQUIRE(Z && emb && h, HGNN_ERR_NULLPTR, "embed_fwd: null pointer");
   ProfScope ps(PT_EMBED, st);
-  k_embed_fwd<<<nb64((int64_t)N * (H / 4), 256), 256, 0, st>>>(N, H, Z, emb, h);
+  if (valid_H(H)) k_embed_fwd<<<nb64((int64_t)N * (H / 4), 256), 256, 0, st>>>(N, H, Z, emb, h);
+  else k_embed_fwd_any<<<nb64((int64_t)N * H, 256), 256, 0, st>>>(N, H, Z, emb, h);
   HGNN_LAUNCH_CHECK("k_embed_fwd");
   return HGNN_OK;
 }
 
 extern "C" int32_t hgnn_embed_bwd_workspace_bytes(int32_t N, int32_t H, size_t* ws_bytes_host) {
-  HGNN_REQUIRE(N >= 0 && valid_H(H), HGNN_ERR_BAD_SHAPE, "embed_bwd: bad N or H");
+  HGNN_REQUIRE(N >= 0 && any_H(H), HGNN_ERR_BAD_SHAPE, "embed_bwd: bad N or H");
   HGNN_REQUIRE(ws_bytes_host, HGNN_ERR_NULLPTR, "null size pointer");
   const size_t nchunk = ((size_t)N + EMB_CHUNK - 1) / EMB_CHUNK;
   *ws_bytes_host = align_up((nchunk > 0 ? nchunk : 1) * (HGNN_ZMAX + 1) * H * sizeof(float));
@@ -387,7 +425,7 @@ extern "C" int32_t hgnn_embed_bwd_workspace_bytes(int32_t N, int32_t H, size_t* 
 extern "C" int32_t hgnn_embed_bwd(void* stream, int32_t N, int32_t H, const int32_t* Z, const float* g_h, float* g_emb,
                                   void* ws, size_t ws_bytes) {
   hipStream_t st = static_cast<hipStream_t>(stream);
-  HGNN_REQUIRE(N >= 0 && valid_H(H), HGNN_ERR_BAD_SHAPE, "embed_bwd: bad N or H");
+  HGNN_REQUIRE(N >= 0 && any_H(H), HGNN_ERR_BAD_SHAPE, "embed_bwd: bad N or H");
   HGNN_REQUIRE(g_emb && ws && (N == 0 || (Z && g_h)), HGNN_ERR_NULLPTR, "embed_bwd: null pointer");
   size_t need = 0;
   HGNN_TRY(hgnn_embed_bwd_workspace_bytes(N, H, &need));
@@ -395,7 +433,8 @@ extern "C" int32_t hgnn_embed_bwd(void* stream, int32_t N, int32_t H, const int3
   const int nchunk = (N + EMB_CHUNK - 1) / EMB_CHUNK;
   ProfScope ps(PT_EMBED, st);
   if (nchunk > 0) {
-    k_embed_bwd_part<<<dim3(HGNN_ZMAX + 1, nchunk), 256, 0, st>>>(N, H, Z, g_h, static_cast<float*>(ws));
+    if (valid_H(H)) k_embed_bwd_part<<<dim3(HGNN_ZMAX + 1, nchunk), 256, 0, st>>>(N, H, Z, g_h, static_cast<float*>(ws));
+    else k_embed_bwd_part_any<<<dim3(HGNN_ZMAX + 1, nchunk), 256, 0, st>>>(N, H, Z, g_h, static_cast<float*>(ws));
     HGNN_LAUNCH_CHECK("k_embed_bwd_part");
   }
   k_embed_bwd_sum<<<((HGNN_ZMAX + 1) * H + 255) / 256, 256, 0, st>>>(nchunk, H, static_cast<const float*>(ws), g_emb);
@@ -406,12 +445,13 @@ extern "C" int32_t hgnn_embed_bwd(void* stream, int32_t N, int32_t H, const int3
 extern "C" int32_t hgnn_pool_by_graph_fwd(void* stream, int32_t N, int32_t G, int32_t H, int32_t mode,
                                           const int32_t* graph_off, const float* h, float* p) {
   hipStream_t st = static_cast<hipStream_t>(stream);
-  HGNN_REQUIRE(N >= 0 && G >= 0 && valid_H(H), HGNN_ERR_BAD_SHAPE, "pool_fwd: bad N, G or H");
+  HGNN_REQUIRE(N >= 0 && G >= 0 && any_H(H), HGNN_ERR_BAD_SHAPE, "pool_fwd: bad N, G or H");
   HGNN_REQUIRE(mode == HGNN_POOL_SUM || mode == HGNN_POOL_MEAN, HGNN_ERR_BAD_SHAPE, "pool_fwd: unknown mode");
   if (G == 0) return HGNN_OK;
   HGNN_REQUIRE(graph_off && p && (h || N == 0), HGNN_ERR_NULLPTR, "pool_fwd: null pointer");
   ProfScope ps(PT_POOL, st);
-  k_pool_fwd<<<G, 1024, 0, st>>>(H, mode, graph_off, h, p);
+  if (valid_H(H)) k_pool_fwd<<<G, 1024, 0, st>>>(H, mode, graph_off, h, p);
+  else k_pool_fwd_any<<<G, 256, 0, st>>>(H, mode, graph_off, h, p);
   HGNN_LAUNCH_CHECK("k_pool_fwd");
   return HGNN_OK;
 }
@@ -419,12 +459,13 @@ extern "C" int32_t hgnn_pool_by_graph_fwd(void* stream, int32_t N, int32_t G, in
 extern "C" int32_t hgnn_pool_by_graph_bwd(void* stream, int32_t N, int32_t G, int32_t H, int32_t mode,
                                           const int32_t* graph_off, const float* g_p, float* g_h, int32_t accumulate) {
   hipStream_t st = static_cast<hipStream_t>(stream);
-  HGNN_REQUIRE(N >= 0 && G >= 0 && valid_H(H), HGNN_ERR_BAD_SHAPE, "pool_bwd: bad N, G or H");
+  HGNN_REQUIRE(N >= 0 && G >= 0 && any_H(H), HGNN_ERR_BAD_SHAPE, "pool_bwd: bad N, G or H");
   HGNN_REQUIRE(mode == HGNN_POOL_SUM || mode == HGNN_POOL_MEAN, HGNN_ERR_BAD_SHAPE, "pool_bwd: unknown mode");
   if (N == 0) return HGNN_OK;
   HGNN_REQUIRE(G > 0 && graph_off && g_p && g_h, HGNN_ERR_NULLPTR, "pool_bwd: null pointer");
   ProfScope ps(PT_POOL, st);
-  k_pool_bwd<<<nb64((int64_t)N * (H / 4), 256), 256, 0, st>>>(N, G, H, mode, graph_off, g_p, g_h, accumulate);
+  if (valid_H(H)) k_pool_bwd<<<nb64((int64_t)N * (H / 4), 256), 256, 0, st>>>(N, G, H, mode, graph_off, g_p, g_h, accumulate);
+  else k_pool_bwd_any<<<nb64((int64_t)N * H, 256), 256, 0, st>>>(N, G, H, mode, graph_off, g_p, g_h, accumulate);
   HGNN_LAUNCH_CHECK("k_pool_bwd");
   return HGNN_OK;
 }

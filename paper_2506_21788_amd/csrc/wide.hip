@@ -14,53 +14,28 @@
 #include "wide.h"
 
 #include "devmath.h"
+#include "frag.h"
 #include "edge_fused.h"
 #include "edgeops.h"
 
 namespace hgnn {
 
-enum { EPI_T = 0, EPI_ROW = 1, EPI_PART = 2 };
-
 // row of slot u of lane half g in the 16-row group rb16 (the accumulator layout of the 32x32 matrix-core tile)
 __device__ __forceinline__ int tset_row(int rb16, int g, int u) { return rb16 * 16 + 8 * (u >> 2) + 4 * g + (u & 3); }
+// rows of group grp are the positions ptr[grp] .. ptr[grp+1]; in fragment tensors every group starts at a multiple
+// of 256 rows: pad0 = first padded row of the group
+__device__ __forceinline__ void group_range(const int32_t* ptr, int grp, int& pos0, int& n, int& pad0) {
+  pad0 = 0;
+  for (int t = 0; t < grp; ++t) pad0 += (ptr[t + 1] - ptr[t] + 255) / 256 * 256;
+  pos0 = ptr[grp];
+  n = ptr[grp + 1] - pos0;
+}
 __device__ __forceinline__ float bf_lo(unsigned w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf_hi(unsigned w) { return __uint_as_float(w & 0xffff0000u); }
 
 // ---------------------------------------------------------------------------------------------
 // fragment GEMM
 // ---------------------------------------------------------------------------------------------
-struct FGemmArgs {
-  const char* A = nullptr;   // fragment (i, kb) at A + (i * a_si + kb * a_sk) KiB
-  long a_si = 0, a_sk = 0;
-  const char* B = nullptr;
-  long b_sj = 0, b_sk = 0;
-  int nI = 0, nJ = 0;        // 32-blocks of the two free dimensions (multiples of the workgroup tile)
-  int nkb = 0;               // 16-blocks of the contraction (even)
-  int kper = 0;              // per split (even)
-  int nsplit = 1;
-  // EPI_T: bf16 T fragments, t_ncb column blocks per row group
-  char* T = nullptr;
-  int t_ncb = 0;
-  // EPI_ROW
-  int M = 0;                 // valid rows
-  float* Cf = nullptr;       // fp32 out, columns < ncol_f
-  long ldc = 0;
-  int ncol_f = 0;
-  unsigned short* Cb = nullptr;   // bf16 out, all columns of the tile
-  long ldcb = 0;
-  const float* r1 = nullptr;      // residuals added to Cf (columns < ncol_f)
-  long ld1 = 0;
-  const float* r2 = nullptr;
-  long ld2 = 0;
-  // EPI_T and EPI_ROW: bias[col] for col < nbias
-  const float* bias = nullptr;
-  int nbias = 0;
-  // EPI_PART: fp32 partial[split][row][col]
-  float* P = nullptr;
-  long ldp = 0, split_stride = 0;
-  int tag = PT_GEMM_NODE;
-};
-
 template <int WI, int WJ>
 struct FCfg {
   static constexpr int KC = 2;               // contraction blocks staged per step
@@ -78,9 +53,28 @@ __global__ void __launch_bounds__(256, (WI * WJ <= 8 ? 2 : 1)) k_fgemm(FGemmArgs
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wi = wave >> 1, wj = wave & 1;
-  const int i0 = blockIdx.y * C::TI, j0 = blockIdx.x * C::TJ;
-  const int kbeg = blockIdx.z * p.kper;
-  const int kend = kbeg + p.kper < p.nkb ? kbeg + p.kper : p.nkb;
+  int i0 = blockIdx.y * C::TI;
+  const int j0 = blockIdx.x * C::TJ;
+  // blockIdx.z: (group, split) for split partials, else the group
+  const int grp = EPI == EPI_PART ? blockIdx.z / p.nsplit : blockIdx.z;
+  const int split = EPI == EPI_PART ? blockIdx.z % p.nsplit : 0;
+  int mvalid = p.M, pos0 = 0, pad0 = 0, kbase = 0, knum = p.nkb;
+  if (p.grp_ptr) {
+    int n;
+    group_range(p.grp_ptr, grp, pos0, n, pad0);
+    const int npad = (n + 255) / 256 * 256;
+    if (EPI == EPI_PART) {
+      kbase = pad0 / 16;
+      knum = npad / 16;
+    } else {
+      if ((int)blockIdx.y * C::TI * 32 >= npad) return;   // uniform over the workgroup, before any barrier
+      i0 += pad0 / 32;
+      mvalid = pad0 + n;
+    }
+  }
+  const int kbeg = kbase + split * p.kper;
+  const int kend = kbeg + p.kper < kbase + knum ? kbeg + p.kper : kbase + knum;
+  const char* Bg = p.B + (long)grp * p.b_grp_stride;
 
   // pass s copies fragment f = 4 s + wave of the step: first the KC x TI fragments of A, then the KC x TJ of B
   const char* src[C::PASSES];
@@ -95,7 +89,7 @@ __global__ void __launch_bounds__(256, (WI * WJ <= 8 ? 2 : 1)) k_fgemm(FGemmArgs
     } else {
       const int f2 = f - C::KC * C::TI;
       const int kk = f2 / C::TJ, jj = f2 % C::TJ;
-      src[s] = p.B + ((long)(j0 + jj) * p.b_sj + (long)kk * p.b_sk) * 1024 + lane * 16;
+      src[s] = Bg + ((long)(j0 + jj) * p.b_sj + (long)kk * p.b_sk) * 1024 + lane * 16;
       kst[s] = p.b_sk * 1024;
     }
   }
@@ -147,7 +141,7 @@ __global__ void __launch_bounds__(256, (WI * WJ <= 8 ? 2 : 1)) k_fgemm(FGemmArgs
     const int jb = j0 + wj * WJ + j;
     const int colx = jb * 32 + x;
     float bv = 0.f;
-    if (EPI != EPI_PART && p.bias && colx < p.nbias) bv = p.bias[colx];
+    if (EPI != EPI_PART && p.bias && colx < p.nbias) bv = p.bias[(long)grp * p.bias_grp_stride + colx];
 #pragma unroll
     for (int i = 0; i < WI; ++i) {
       const int ib = i0 + wi * WI + i;
@@ -164,19 +158,20 @@ __global__ void __launch_bounds__(256, (WI * WJ <= 8 ? 2 : 1)) k_fgemm(FGemmArgs
       } else if constexpr (EPI == EPI_ROW) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-          const int row = ib * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
-          if (row < p.M) {
+          const int prow = ib * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
+          if (prow < mvalid) {
+            const long row = p.row_idx ? p.row_idx[pos0 + prow - pad0] : prow;   // scatter to the caller's rows
             float val = acc[i][j][v] + bv;
             if (p.Cf && colx < p.ncol_f) {
-              if (p.r1) val += p.r1[(long)row * p.ld1 + colx];
-              if (p.r2) val += p.r2[(long)row * p.ld2 + colx];
-              p.Cf[(long)row * p.ldc + colx] = val;
+              if (p.r1) val += p.r1[row * p.ld1 + colx];
+              if (p.r2) val += p.r2[row * p.ld2 + colx];
+              p.Cf[row * p.ldc + colx] = val;
             }
-            if (p.Cb) p.Cb[(long)row * p.ldcb + colx] = (unsigned short)f2bf_bits(val);
+            if (p.Cb) p.Cb[row * p.ldcb + colx] = (unsigned short)f2bf_bits(val);
           }
         }
       } else {
-        float* out = p.P + (long)blockIdx.z * p.split_stride;
+        float* out = p.P + (long)blockIdx.z * p.split_stride;   // [group][split]
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
           const int row = ib * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
@@ -194,10 +189,12 @@ static int32_t launch_fgemm_t(hipStream_t st, const FGemmArgs& a) {
                HGNN_ERR_BAD_SHAPE, "fragment GEMM: %d x %d blocks, %d contraction blocks do not tile", a.nI, a.nJ, a.nkb);
   if (a.nI == 0 || a.nJ == 0) return HGNN_OK;
   const int nsplit = a.nkb == 0 ? 1 : (a.nkb + a.kper - 1) / a.kper;
-  HGNN_REQUIRE(nsplit == a.nsplit, HGNN_ERR_BAD_SHAPE, "fragment GEMM: split count mismatch");
-  HGNN_REQUIRE(a.nI / C::TI <= 65535 && nsplit <= 65535, HGNN_ERR_OVERFLOW, "fragment GEMM: grid too large");
+  HGNN_REQUIRE(nsplit == a.nsplit && (EPI == EPI_PART || nsplit == 1), HGNN_ERR_BAD_SHAPE,
+               "fragment GEMM: split count mismatch");
+  const int groups = a.grp_ptr ? a.S : 1;
+  HGNN_REQUIRE(a.nI / C::TI <= 65535 && (long)nsplit * groups <= 65535, HGNN_ERR_OVERFLOW, "fragment GEMM: grid too large");
   ProfScope ps(a.tag, st);
-  k_fgemm<WI, WJ, EPI><<<dim3(a.nJ / C::TJ, a.nI / C::TI, nsplit), 256, C::LDS_BYTES, st>>>(a);
+  k_fgemm<WI, WJ, EPI><<<dim3(a.nJ / C::TJ, a.nI / C::TI, nsplit * groups), 256, C::LDS_BYTES, st>>>(a);
   HGNN_LAUNCH_CHECK("k_fgemm");
   return HGNN_OK;
 }
@@ -205,38 +202,24 @@ static int32_t launch_fgemm_t(hipStream_t st, const FGemmArgs& a) {
 // ---------------------------------------------------------------------------------------------
 // weights -> B fragments:  fragment (nb, kb) of the destination, lane (g, x), slot u  =  B[16 kb + 8 g + u][32 nb + x]
 // ---------------------------------------------------------------------------------------------
-struct PackPart {
-  long src_off;        // B[k][n] = src[src_off + k * sk + n * sn] for k < K, n < Nn, else 0
-  int sk, sn;
-  int kb0, nb0;        // where the part's (Hp/16 x Hp/32) fragments sit in the destination
-};
-struct PackFragArgs {
-  const float* src;
-  unsigned short* dst;
-  int nkb_total;       // fragments per column block of the destination
-  int K, Nn;           // valid extent of every part
-  int Hp;
-  int nparts;
-  PackPart part[4];
-};
-
 __global__ void __launch_bounds__(256) k_pack_frag(PackFragArgs a) {
   const PackPart pt = a.part[blockIdx.y];
   const long idx = (long)blockIdx.x * 256 + threadIdx.x;   // element of the part: [nb][kb][lane][u]
-  const int nkb = a.Hp / 16;
-  if (idx >= (long)a.Hp * a.Hp) return;
+  const int nkb = a.Kp / 16;
+  if (idx >= (long)a.Kp * a.Np) return;
   const int u = idx & 7, lane = (idx >> 3) & 63;
   const int f = (int)(idx >> 9);
   const int kb = f % nkb, nb = f / nkb;
   const int k = kb * 16 + (lane >> 5) * 8 + u, n = nb * 32 + (lane & 31);
   float v = 0.f;
-  if (k < a.K && n < a.Nn) v = a.src[pt.src_off + (long)k * pt.sk + (long)n * pt.sn];
-  a.dst[(((long)(pt.nb0 + nb) * a.nkb_total + pt.kb0 + kb) * 64 + lane) * 8 + u] = (unsigned short)f2bf_bits(v);
+  if (k < a.K && n < a.Nn) v = a.src[blockIdx.z * a.src_grp_stride + pt.src_off + (long)k * pt.sk + (long)n * pt.sn];
+  a.dst[blockIdx.z * a.dst_grp_stride + (((long)(pt.nb0 + nb) * a.nkb_total + pt.kb0 + kb) * 64 + lane) * 8 + u] =
+      (unsigned short)f2bf_bits(v);
 }
 
-static int32_t launch_pack_frag(hipStream_t st, const PackFragArgs& a) {
+int32_t launch_pack_frag(hipStream_t st, const PackFragArgs& a) {
   ProfScope ps(PT_PACK, st);
-  k_pack_frag<<<dim3((unsigned)(((long)a.Hp * a.Hp + 255) / 256), a.nparts), 256, 0, st>>>(a);
+  k_pack_frag<<<dim3((unsigned)(((long)a.Kp * a.Np + 255) / 256), a.nparts, a.groups), 256, 0, st>>>(a);
   HGNN_LAUNCH_CHECK("k_pack_frag");
   return HGNN_OK;
 }
@@ -244,45 +227,36 @@ static int32_t launch_pack_frag(hipStream_t st, const PackFragArgs& a) {
 // ---------------------------------------------------------------------------------------------
 // row-major fp32 -> fragments.  mode 0: x, 1: silu(x), 2: x * silu'(z)
 // ---------------------------------------------------------------------------------------------
-struct ToFragArgs {
-  const float* X = nullptr;
-  long ldx = 0;
-  const float* Z = nullptr;
-  long ldz = 0;
-  int mode = 0;
-  int M = 0;          // valid rows
-  int Mp = 0;         // rows covered (multiple of 32), rows >= M give zeros
-  int ncol = 0;       // valid columns
-  int Cp = 0;         // columns covered (multiple of 32), columns >= ncol give zeros
-  char* R = nullptr;  // R fragments: r_nkb contraction blocks per row block, this tensor starts at block r_kb0
-  int r_nkb = 0, r_kb0 = 0;
-  char* T = nullptr;  // T fragments: t_ncb column blocks per row group, this tensor starts at block t_cb0
-  int t_ncb = 0, t_cb0 = 0;
-};
-
 __global__ void __launch_bounds__(256) k_to_frag(ToFragArgs a) {
   const int CG = a.Cp >> 3;
   const long idx = (long)blockIdx.x * 256 + threadIdx.x;
   const int cg = (int)(idx % CG);
-  const long rs = idx / CG;   // row set: 16-row group rs >> 1, lane half rs & 1
-  if (rs >= a.Mp / 8) return;
-  const int rb16 = (int)(rs >> 1), g = (int)(rs & 1);
+  const long rs = idx / CG;   // row set of the group: 16-row group rs >> 1, lane half rs & 1
+  int pos0 = 0, pad0 = 0, n = a.M, npad = a.Mp;
+  if (a.grp_ptr) {
+    group_range(a.grp_ptr, blockIdx.y, pos0, n, pad0);
+    npad = (n + 255) / 256 * 256;
+  }
+  if (rs >= npad / 8) return;
+  const int g = (int)(rs & 1);
   const int c0 = cg * 8;
   unsigned short vals[8][8];   // [u][k]
 #pragma unroll
   for (int u = 0; u < 8; ++u) {
-    const int r = tset_row(rb16, g, u);
+    const int r = tset_row((int)(rs >> 1), g, u);
+    const long sr = r < n ? (a.row_idx ? a.row_idx[pos0 + r] : pad0 + r) : 0;
 #pragma unroll
     for (int k = 0; k < 8; ++k) {
       float v = 0.f;
-      if (r < a.M && c0 + k < a.ncol) {
-        v = a.X[(long)r * a.ldx + c0 + k];
+      if (r < n && c0 + k < a.ncol) {
+        v = a.X[sr * a.ldx + c0 + k];
         if (a.mode == 1) v = silu_f(v);
-        else if (a.mode == 2) v *= dsilu_f(a.Z[(long)r * a.ldz + c0 + k]);
+        else if (a.mode == 2) v *= dsilu_f(a.Z[sr * a.ldz + c0 + k]);
       }
       vals[u][k] = (unsigned short)f2bf_bits(v);
     }
   }
+  const int rb16 = (int)(rs >> 1) + pad0 / 16;   // destination rows are the padded ones
   if (a.R) {
 #pragma unroll
     for (int u = 0; u < 8; ++u) {
@@ -310,12 +284,12 @@ __global__ void __launch_bounds__(256) k_to_frag(ToFragArgs a) {
   }
 }
 
-static int32_t launch_to_frag(hipStream_t st, const ToFragArgs& a) {
-  HGNN_REQUIRE(a.Mp % 32 == 0 && a.Cp % 32 == 0, HGNN_ERR_BAD_SHAPE, "to_frag: padded extents must be multiples of 32");
+int32_t launch_to_frag(hipStream_t st, const ToFragArgs& a) {
+  HGNN_REQUIRE(a.Mp % 256 == 0 && a.Cp % 32 == 0, HGNN_ERR_BAD_SHAPE, "to_frag: padded extents do not tile");
   const long n = (long)(a.Mp / 8) * (a.Cp / 8);
   if (n == 0) return HGNN_OK;
   ProfScope ps(PT_MISC, st);
-  k_to_frag<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(a);
+  k_to_frag<<<dim3((unsigned)((n + 255) / 256), a.grp_ptr ? a.S : 1), 256, 0, st>>>(a);
   HGNN_LAUNCH_CHECK("k_to_frag");
   return HGNN_OK;
 }
@@ -323,64 +297,74 @@ static int32_t launch_to_frag(hipStream_t st, const ToFragArgs& a) {
 // ---------------------------------------------------------------------------------------------
 // column sums of small row-major tensors and ordered reduction of per-block partial rows
 // ---------------------------------------------------------------------------------------------
-// dest[c] = sum over s < nsplit (ascending) of partial[s * stride + c], c < ncol
+// dest[c] = sum over s < nsplit (ascending) of partial[s * stride + c], c < ncol   (blockIdx.y: group)
 __global__ void __launch_bounds__(256) k_reduce_cols(const float* __restrict__ partial, int nsplit, long stride,
-                                                     int ncol, float* __restrict__ dest) {
+                                                     int ncol, float* __restrict__ dest, long partial_grp_stride,
+                                                     long dest_grp_stride) {
   const int c = blockIdx.x * 256 + threadIdx.x;
   if (c >= ncol) return;
+  const float* p = partial + blockIdx.y * partial_grp_stride;
   float s = 0.f;
-  for (int k = 0; k < nsplit; ++k) s += partial[(long)k * stride + c];
-  dest[c] = s;
+  for (int k = 0; k < nsplit; ++k) s += p[(long)k * stride + c];
+  dest[blockIdx.y * dest_grp_stride + c] = s;
 }
-static int32_t launch_reduce_cols(hipStream_t st, const float* partial, int nsplit, long stride, int ncol, float* dest) {
-  k_reduce_cols<<<(ncol + 255) / 256, 256, 0, st>>>(partial, nsplit, stride, ncol, dest);
+static int32_t launch_reduce_cols(hipStream_t st, const float* partial, int nsplit, long stride, int ncol, float* dest,
+                                  int groups = 1, long partial_grp_stride = 0, long dest_grp_stride = 0) {
+  k_reduce_cols<<<dim3((ncol + 255) / 256, groups), 256, 0, st>>>(partial, nsplit, stride, ncol, dest, partial_grp_stride,
+                                                                  dest_grp_stride);
   HGNN_LAUNCH_CHECK("k_reduce_cols");
   return HGNN_OK;
 }
 
 constexpr int CS_ROWS = 64;   // rows per partial of k_colsum_rows
-// partial[split][c] = sum over the split's rows of f(X[r][c]);  mode as in k_to_frag
-__global__ void __launch_bounds__(256) k_colsum_rows(const float* __restrict__ X, long ldx, const float* __restrict__ Z,
-                                                     long ldz, int mode, int M, int ncol, float* __restrict__ partial,
-                                                     long stride) {
+// partial[group][split][c] = sum over the split's rows of w * f(X[r][c])   (blockIdx.y: split, blockIdx.z: group)
+__global__ void __launch_bounds__(256) k_colsum_rows(ColsumRowsArgs a, int nsplit) {
   const int c = blockIdx.x * 256 + threadIdx.x;
-  if (c >= ncol) return;
+  if (c >= a.ncol) return;
+  int pos0 = 0, pad0 = 0, n = a.M;
+  if (a.grp_ptr) group_range(a.grp_ptr, blockIdx.z, pos0, n, pad0);
   const int r0 = blockIdx.y * CS_ROWS;
-  const int r1 = r0 + CS_ROWS < M ? r0 + CS_ROWS : M;
+  const int r1 = r0 + CS_ROWS < n ? r0 + CS_ROWS : n;
   float s = 0.f;
   for (int r = r0; r < r1; ++r) {
-    float v = X[(long)r * ldx + c];
-    if (mode == 1) v = silu_f(v);
-    else if (mode == 2) v *= dsilu_f(Z[(long)r * ldz + c]);
+    const long sr = a.row_idx ? a.row_idx[pos0 + r] : pad0 + r;
+    float v = a.X[sr * a.ldx + c];
+    if (a.mode == 1) v = silu_f(v);
+    else if (a.mode == 2) v *= dsilu_f(a.Z[sr * a.ldz + c]);
+    if (a.w) v *= a.w[sr];
     s += v;
   }
-  partial[(long)blockIdx.y * stride + c] = s;
+  a.partial[((long)blockIdx.z * nsplit + blockIdx.y) * a.ncol + c] = s;
 }
-static size_t colsum_rows_partial_floats(int M, int Hp) { return (size_t)((M + CS_ROWS - 1) / CS_ROWS + 1) * Hp; }
-static int32_t launch_colsum_rows(hipStream_t st, const float* X, long ldx, const float* Z, long ldz, int mode, int M,
-                                  int ncol, int Hp, float* partial, float* dest) {
+size_t colsum_rows_partial_floats(int M, int ncol, int S) {
+  return (size_t)((M + CS_ROWS - 1) / CS_ROWS + 1) * ncol * (S < 1 ? 1 : S);
+}
+int32_t launch_colsum_rows(hipStream_t st, const ColsumRowsArgs& a) {
   ProfScope ps(PT_COLSUM, st);
-  const int ns = (M + CS_ROWS - 1) / CS_ROWS;
+  const int ns = (a.M + CS_ROWS - 1) / CS_ROWS;
+  const int groups = a.grp_ptr ? a.S : 1;
   if (ns > 0) {
-    k_colsum_rows<<<dim3((ncol + 255) / 256, ns), 256, 0, st>>>(X, ldx, Z, ldz, mode, M, ncol, partial, Hp);
+    k_colsum_rows<<<dim3((a.ncol + 255) / 256, ns, groups), 256, 0, st>>>(a, ns);
     HGNN_LAUNCH_CHECK("k_colsum_rows");
   }
-  return launch_reduce_cols(st, partial, ns, Hp, ncol, dest);
+  return launch_reduce_cols(st, a.partial, ns, a.ncol, a.ncol, a.dest, groups, (long)ns * a.ncol, a.dest_grp_stride);
 }
 
-// dest[pa * strideA + pb * strideB + r1 * H + r2] = sum over splits (ascending) of partial[s][k1][k2],
-// k1 = pa * Hp + r1, k2 = pb * Hp + r2; padding rows / columns (r >= H) are dropped
+// dest[group * dest_grp_stride + pa * strideA + pb * strideB + r1 * HB + r2] = sum over splits (ascending) of
+// partial[group][s][k1][k2], k1 = pa * HpA + r1, k2 = pb * HpB + r2; padding (r1 >= HA or r2 >= HB) is dropped
 __global__ void __launch_bounds__(256) k_reduce_wgrad(const float* __restrict__ partial, int nsplit, long split_stride,
-                                                      int K1p, int K2p, int Hp, int H, float* __restrict__ dest,
-                                                      long strideA, long strideB) {
+                                                      int K1p, int K2p, int HpA, int HA, int HpB, int HB,
+                                                      float* __restrict__ dest, long strideA, long strideB,
+                                                      long dest_grp_stride) {
   const long idx = (long)blockIdx.x * 256 + threadIdx.x;
   if (idx >= (long)K1p * K2p) return;
   const int k1 = (int)(idx / K2p), k2 = (int)(idx % K2p);
-  const int pa = k1 / Hp, r1 = k1 % Hp, pb = k2 / Hp, r2 = k2 % Hp;
-  if (r1 >= H || r2 >= H) return;
+  const int pa = k1 / HpA, r1 = k1 % HpA, pb = k2 / HpB, r2 = k2 % HpB;
+  if (r1 >= HA || r2 >= HB) return;
+  const float* p = partial + (long)blockIdx.y * nsplit * split_stride;
   float s = 0.f;
-  for (int k = 0; k < nsplit; ++k) s += partial[(long)k * split_stride + idx];
-  dest[pa * strideA + pb * strideB + (long)r1 * H + r2] = s;
+  for (int k = 0; k < nsplit; ++k) s += p[(long)k * split_stride + idx];
+  dest[blockIdx.y * dest_grp_stride + pa * strideA + pb * strideB + (long)r1 * HB + r2] = s;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -803,7 +787,6 @@ struct WideWs {
   size_t partial_floats;
   size_t bytes;
 };
-constexpr int WIDE_MAX_SPLITS = 24;
 static WideWs carve_ws_w(void* p, const WideDims& d) {
   Carver c(p);
   WideWs w;
@@ -821,8 +804,8 @@ static WideWs carve_ws_w(void* p, const WideDims& d) {
   w.ga1_T = c.take<char>(d.edge_bytes());
   w.cvec = c.take<float>((size_t)d.E + 4);
   w.colpart = c.take<float>((size_t)ELEM_MAX_BLOCKS * 2 * d.Hp);
-  w.cs_partial = c.take<float>(colsum_rows_partial_floats(d.N, d.Hp));
-  w.partial_floats = (size_t)WIDE_MAX_SPLITS * 2 * d.Hp * d.Hp;
+  w.cs_partial = c.take<float>(colsum_rows_partial_floats(d.N, d.Hp, 1));
+  w.partial_floats = (size_t)24 * 2 * d.Hp * d.Hp;
   w.partial = c.take<float>(w.partial_floats);
   w.bytes = c.used();
   return w;
@@ -844,19 +827,19 @@ static FGemmArgs nn_args(const char* A_R, int a_nkb, int nI, const unsigned shor
   return g;
 }
 
-// dest = A^T B over `rows` rows (T fragments: A with a_ncb column blocks of which nI from block a_cb0 are used; B alike),
-// split over the rows, partials reduced in order into the caller's [.., H, H] weight-gradient blocks
-static int32_t wgrad_w(hipStream_t st, const WideDims& d, const char* A_T, int a_ncb, int a_cb0, int nI, const char* B_T,
-                       int b_ncb, int b_cb0, int nJ, int64_t rows, float* partial, size_t partial_floats, float* dest,
-                       long strideA, long strideB, int tag) {
+constexpr int WIDE_MAX_SPLITS = 24;
+int32_t launch_fwgrad(hipStream_t st, const FWgradArgs& a) {
   FGemmArgs g;
-  g.A = A_T + (long)a_cb0 * 1024; g.a_si = 1; g.a_sk = a_ncb;
-  g.B = B_T + (long)b_cb0 * 1024; g.b_sj = 1; g.b_sk = b_ncb;
-  g.nI = nI; g.nJ = nJ;
-  g.nkb = (int)(rows / 16);
-  const long tiles = (long)(nI / 4) * (nJ / 4);
+  g.A = a.A_T + (long)a.a_cb0 * 1024; g.a_si = 1; g.a_sk = a.a_ncb;
+  g.B = a.B_T + (long)a.b_cb0 * 1024; g.b_sj = 1; g.b_sk = a.b_ncb;
+  g.nI = a.nI; g.nJ = a.nJ;
+  g.nkb = (int)(a.rows / 16);
+  g.grp_ptr = a.grp_ptr; g.S = a.S;
+  const int groups = a.grp_ptr ? a.S : 1;
+  // enough splits for about three workgroups per CU, as many as the partial buffer holds
+  const long tiles = (long)(a.nI / 4) * (a.nJ / 4) * groups;
   long want = (3L * num_cus() + tiles - 1) / tiles;
-  const long cap = (long)(partial_floats / ((size_t)nI * 32 * nJ * 32));
+  const long cap = (long)(a.partial_floats / ((size_t)a.nI * 32 * a.nJ * 32 * groups));
   if (want > cap) want = cap;
   if (want > WIDE_MAX_SPLITS) want = WIDE_MAX_SPLITS;
   if (want < 1) want = 1;
@@ -865,17 +848,42 @@ static int32_t wgrad_w(hipStream_t st, const WideDims& d, const char* A_T, int a
   if (kper < 2) kper = 2;
   g.kper = kper;
   g.nsplit = g.nkb == 0 ? 1 : (g.nkb + kper - 1) / kper;
-  g.P = partial; g.ldp = (long)nJ * 32; g.split_stride = (long)nI * 32 * nJ * 32;
-  g.tag = tag;
-  HGNN_REQUIRE((size_t)g.nsplit * g.split_stride <= partial_floats, HGNN_ERR_WORKSPACE_TOO_SMALL,
+  g.P = a.partial; g.ldp = (long)a.nJ * 32; g.split_stride = (long)a.nI * 32 * a.nJ * 32;
+  g.tag = a.tag;
+  HGNN_REQUIRE((size_t)g.nsplit * groups * g.split_stride <= a.partial_floats, HGNN_ERR_WORKSPACE_TOO_SMALL,
                "weight-gradient partials do not fit the workspace");
   HGNN_TRY((launch_fgemm_t<2, 2, EPI_PART>(st, g)));
-  ProfScope ps(tag, st);
+  ProfScope ps(a.tag, st);
   const long n = g.split_stride;
-  k_reduce_wgrad<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(partial, g.nkb == 0 ? 0 : g.nsplit, g.split_stride, nI * 32,
-                                                              nJ * 32, d.Hp, d.H, dest, strideA, strideB);
+  k_reduce_wgrad<<<dim3((unsigned)((n + 255) / 256), groups), 256, 0, st>>>(
+      a.partial, g.nsplit, g.split_stride, a.nI * 32, a.nJ * 32, a.HpA, a.HA, a.HpB, a.HB, a.dest, a.strideA, a.strideB,
+      a.dest_grp_stride);
   HGNN_LAUNCH_CHECK("k_reduce_wgrad");
   return HGNN_OK;
+}
+int32_t launch_fgemm_rows(hipStream_t st, const FGemmArgs& a) { return launch_fgemm_t<4, 2, EPI_ROW>(st, a); }
+int32_t launch_fgemm_rows_T(hipStream_t st, const FGemmArgs& a) { return launch_fgemm_t<4, 2, EPI_T>(st, a); }
+
+// layer-level shorthand: square Hp blocks, no groups
+static int32_t wgrad_w(hipStream_t st, const WideDims& d, const char* A_T, int a_ncb, int a_cb0, int nI, const char* B_T,
+                       int b_ncb, int b_cb0, int nJ, int64_t rows, float* partial, size_t partial_floats, float* dest,
+                       long strideA, long strideB, int tag) {
+  FWgradArgs a;
+  a.A_T = A_T; a.a_ncb = a_ncb; a.a_cb0 = a_cb0; a.nI = nI;
+  a.B_T = B_T; a.b_ncb = b_ncb; a.b_cb0 = b_cb0; a.nJ = nJ;
+  a.rows = rows;
+  a.HpA = d.Hp; a.HA = d.H; a.HpB = d.Hp; a.HB = d.H;
+  a.partial = partial; a.partial_floats = partial_floats;
+  a.dest = dest; a.strideA = strideA; a.strideB = strideB;
+  a.tag = tag;
+  return launch_fwgrad(st, a);
+}
+static int32_t colsum_w(hipStream_t st, const float* X, long ldx, const float* Z, long ldz, int mode, int M, int ncol,
+                        float* partial, float* dest) {
+  ColsumRowsArgs c;
+  c.X = X; c.ldx = ldx; c.Z = Z; c.ldz = ldz; c.mode = mode; c.M = M; c.ncol = ncol;
+  c.partial = partial; c.dest = dest;
+  return launch_colsum_rows(st, c);
 }
 
 int32_t wide_layer_fwd(hipStream_t st, const WideLayerArgs& a) {
@@ -890,7 +898,7 @@ int32_t wide_layer_fwd(hipStream_t st, const WideLayerArgs& a) {
   // packed (elements): [W1a | W1b] at 0 (K = Hp, 2 ncb column blocks), W2 at 2 PP, [W3a ; W3b] at 3 PP (K = 2 Hp), W4 at 5 PP
   {
     PackFragArgs pk;
-    pk.src = W; pk.K = H; pk.Nn = H; pk.Hp = Hp;
+    pk.src = W; pk.K = H; pk.Nn = H; pk.Kp = Hp; pk.Np = Hp;
     pk.dst = w.packed; pk.nkb_total = d.nkb; pk.nparts = 2;
     pk.part[0] = {o.W1, H, 1, 0, 0};
     pk.part[1] = {o.W1 + HH, H, 1, 0, d.ncb};
@@ -981,7 +989,7 @@ int32_t wide_layer_bwd(hipStream_t st, const WideLayerArgs& a) {
   // [W1a^T ; W1b^T] at 4 PP (K = 2 Hp)
   {
     PackFragArgs pk;
-    pk.src = W; pk.K = H; pk.Nn = H; pk.Hp = Hp;
+    pk.src = W; pk.K = H; pk.Nn = H; pk.Kp = Hp; pk.Np = Hp;
     pk.dst = w.packed; pk.nkb_total = d.nkb; pk.nparts = 1;
     pk.part[0] = {o.W4, 1, H, 0, 0};
     HGNN_TRY(launch_pack_frag(st, pk));
@@ -1020,7 +1028,7 @@ int32_t wide_layer_bwd(hipStream_t st, const WideLayerArgs& a) {
   // g_W4 = a3^T g_h', g_b4 = column sums of g_h'
   HGNN_TRY(wgrad_w(st, d, w.a3_T, d.ncb, 0, d.ncb, w.x_T, d.ncb, 0, d.ncb, d.Np, w.partial, w.partial_floats, gW + o.W4,
                    0, 0, PT_WGRAD_NODE));
-  HGNN_TRY(launch_colsum_rows(st, a.g_h_out, H, nullptr, 0, 0, d.N, H, Hp, w.cs_partial, gW + o.b4));
+  HGNN_TRY(colsum_w(st, a.g_h_out, H, nullptr, 0, 0, d.N, H, w.cs_partial, gW + o.b4));
   {  // g_a3 = g_h' W4^T
     FGemmArgs g = nn_args(w.x_R, d.nkb, d.Np / 32, w.packed, d.ncb, PT_GEMM_NODE);
     g.M = d.N; g.Cf = w.nodeA; g.ldc = Hp; g.ncol_f = Hp;
@@ -1032,7 +1040,7 @@ int32_t wide_layer_bwd(hipStream_t st, const WideLayerArgs& a) {
     t.R = w.x_R; t.r_nkb = d.nkb; t.r_kb0 = 0;
     t.T = w.x_T; t.t_ncb = d.ncb; t.t_cb0 = 0;
     HGNN_TRY(launch_to_frag(st, t));
-    HGNN_TRY(launch_colsum_rows(st, w.nodeA, Hp, s.z3, Hp, 2, d.N, H, Hp, w.cs_partial, gW + o.b3));
+    HGNN_TRY(colsum_w(st, w.nodeA, Hp, s.z3, Hp, 2, d.N, H, w.cs_partial, gW + o.b3));
   }
   // g_W3 = [h ; M]^T g_z3
   HGNN_TRY(wgrad_w(st, d, w.hM_T, 2 * d.ncb, 0, 2 * d.ncb, w.x_T, d.ncb, 0, d.ncb, d.Np, w.partial, w.partial_floats,

@@ -63,9 +63,11 @@ class HotPath:
     """One GPU's share of a training step on one batch: graph -> embed -> L layers -> pool -> heads,
     forward and backward. Inputs are numpy arrays (uploaded once); outputs stay on the device."""
 
-    def __init__(self, batch, rc, H, L, S, dtype, emb, layer_weights, head_weights, alpha=None, Hh=None):
+    def __init__(self, batch, rc, H, L, S, dtype, emb, layer_weights, head_weights, alpha=None, Hh=None, D=None):
+        """D: hidden layers per head (the deep-head entry points); None: the one-hidden-layer heads."""
         self.N, self.G, self.H, self.L, self.S = batch.N, batch.G, H, L, S
         self.Hh = H if Hh is None else Hh
+        self.D = D
         self.dtype = {"f32": B.F32, "bf16": B.BF16}[dtype]
         self.pos = _dev(batch.pos, torch.float32)
         self.Z = _dev(batch.Z, torch.int32)
@@ -96,7 +98,10 @@ class HotPath:
         N, G, H, L, S = self.N, self.G, self.H, self.L, self.S
         f32 = dict(dtype=torch.float32, device="cuda")
         ws_b, saved_b = B.mp_layer_workspace_bytes(N, E, H, self.dtype)
-        hws_b, hsaved_b = B.multihead_decode_workspace_bytes(N, G, H, self.Hh, S, self.dtype)
+        if self.D is None:
+            hws_b, hsaved_b = B.multihead_decode_workspace_bytes(N, G, H, self.Hh, S, self.dtype)
+        else:
+            hws_b, hsaved_b = B.multihead_deep_workspace_bytes(N, G, H, self.Hh, self.D, S, self.dtype)
         self.ws = _bytes(max(ws_b, hws_b, B.embed_bwd_workspace_bytes(N, H)))
         self.saved = [_bytes(saved_b) for _ in range(L)]
         self.hsaved = _bytes(hsaved_b)
@@ -121,14 +126,23 @@ class HotPath:
             B.mp_layer_fwd(N, g.E, H, self.dtype, self.alpha, g.row_ptr, g.dst, g.col, g.d2, g.rvec,
                            self.h[l], self.v[l], self.W[l], self.h[l + 1], self.v[l + 1], self.saved[l], self.ws)
         B.pool_by_graph_fwd(N, G, H, B.POOL_MEAN, self.graph_off, self.h[-1], self.p)
-        B.multihead_decode_fwd(N, G, H, self.Hh, self.S, self.dtype, self.plan, self.p, self.h[-1], self.v[-1],
-                               self.Whead, self.energy, self.force, self.hsaved, self.ws)
+        if self.D is None:
+            B.multihead_decode_fwd(N, G, H, self.Hh, self.S, self.dtype, self.plan, self.p, self.h[-1], self.v[-1],
+                                   self.Whead, self.energy, self.force, self.hsaved, self.ws)
+        else:
+            B.multihead_deep_fwd(N, G, H, self.Hh, self.D, self.S, self.dtype, self.plan, self.p, self.h[-1],
+                                 self.v[-1], self.Whead, self.energy, self.force, self.hsaved, self.ws)
 
     def backward(self, g_energy, g_force):
         g, N, G, H = self.graph, self.N, self.G, self.H
-        B.multihead_decode_bwd(N, G, H, self.Hh, self.S, self.dtype, self.plan, self.p, self.h[-1], self.v[-1],
-                               self.Whead, self.hsaved, g_energy, g_force, self.g_p, self.g_h[0], self.g_v[0],
-                               self.gWhead, self.ws)
+        if self.D is None:
+            B.multihead_decode_bwd(N, G, H, self.Hh, self.S, self.dtype, self.plan, self.p, self.h[-1], self.v[-1],
+                                   self.Whead, self.hsaved, g_energy, g_force, self.g_p, self.g_h[0], self.g_v[0],
+                                   self.gWhead, self.ws)
+        else:
+            B.multihead_deep_bwd(N, G, H, self.Hh, self.D, self.S, self.dtype, self.plan, self.p, self.h[-1],
+                                 self.v[-1], self.Whead, self.hsaved, g_energy, g_force, self.g_p, self.g_h[0],
+                                 self.g_v[0], self.gWhead, self.ws)
         B.pool_by_graph_bwd(N, G, H, B.POOL_MEAN, self.graph_off, self.g_p, self.g_h[0], True)
         cur = 0
         for l in reversed(range(self.L)):

@@ -50,7 +50,23 @@ def test_host_side_argument_checks_need_no_gpu():
     # H outside the supported tile granularity
     rc = lib.hgnn_mp_layer_workspace_bytes(ctypes.c_int32(10), ctypes.c_int64(50), ctypes.c_int32(100),
                                            ctypes.c_int32(0), ctypes.byref(a), ctypes.byref(s))
-    assert rc == -2 and b"64, 128 or 256" in lib.hgnn_last_error_string()
+    assert rc == -2 and b"64, 128, 256 or lie in 257..1024" in lib.hgnn_last_error_string()
+    # widths above 256 exist with bf16 operands only
+    unimpl = [l for l in open(HEADER) if "HGNN_ERR_UNIMPLEMENTED" in l and "=" in l]
+    code = int(re.search(r"=\s*(-?\d+)", unimpl[0]).group(1))
+    rc = lib.hgnn_mp_layer_workspace_bytes(ctypes.c_int32(10), ctypes.c_int64(50), ctypes.c_int32(866),
+                                           ctypes.c_int32(0), ctypes.byref(a), ctypes.byref(s))
+    assert rc == code and b"bf16" in lib.hgnn_last_error_string()
+    rc = lib.hgnn_mp_layer_workspace_bytes(ctypes.c_int32(10), ctypes.c_int64(50), ctypes.c_int32(866),
+                                           ctypes.c_int32(1), ctypes.byref(a), ctypes.byref(s))
+    assert rc == 0 and a.value > 0 and s.value > 0
+    # deep heads: depth range, bf16 only
+    f = lib.hgnn_multihead_deep_workspace_bytes
+    args = lambda H, Hh, D, dt: [ctypes.c_int32(x) for x in (10, 2, H, Hh, D, 3, dt)] + [ctypes.byref(a), ctypes.byref(s)]
+    assert f(*args(866, 889, 3, 1)) == 0 and a.value > 0
+    assert f(*args(866, 889, 0, 1)) == -2
+    assert f(*args(866, 2000, 3, 1)) == -2
+    assert f(*args(866, 889, 3, 0)) == code
     rc = lib.hgnn_mp_layer_workspace_bytes(ctypes.c_int32(10), ctypes.c_int64(50), ctypes.c_int32(128),
                                            ctypes.c_int32(1), ctypes.byref(a), ctypes.byref(s))
     assert rc == 0 and a.value > 0 and s.value >= 50 * 128 * 4
