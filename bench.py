@@ -49,6 +49,13 @@ def kernel_work(tag, N, E, H, dtype):
         return 2.0 * NH * H, 2 * NH * 4
     if tag == "colsum":
         return 0.0, NH * 4
+    # widths above 256 (fragment-GEMM path, bf16): per-edge products run as plain GEMMs over materialised tensors
+    if tag == "frag_gemm_edge":      # in: a1 (or g_z2) + W2; out: z2 (or g_a1)
+        return 2.0 * EH * H, 2 * EH * b + 2.0 * H * H
+    if tag == "frag_wgrad_edge":     # in: a1, g_z2; out: H x H
+        return 2.0 * EH * H, 2 * EH * b + 4.0 * H * H
+    if tag == "edge_elementwise":    # three kernels per layer; on average ~3 edge tensors moved per launch
+        return 0.0, 3 * EH * b + 12.0 * E + 2 * NH * b
     if tag.startswith("neigh"):      # whole graph build: in pos; out col, shift, d2, rvec, dst, permT, offsets
         return 0.0, 12.0 * N + 31.0 * E + 12.0 * N
     return 0.0, 0.0
@@ -256,7 +263,8 @@ def main():
         "ms_per_step": t_full * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": hp["dtype"], "data": "synthetic",
         "config": {"workload": f"{args.config}: {hp['desc']}", "atoms": N, "graphs": G, "edges": E, "H": H,
-                   "layers": L, "sources": hp["S"], "cutoff": hp["rc"], "alpha": hot.alpha},
+                   "layers": L, "sources": hp["S"], "cutoff": hp["rc"], "alpha": hot.alpha,
+                   "head_width": hp.get("Hh", H), "head_hidden_layers": hp.get("D", 1)},
         "edge_layers_per_s": E * L / t_full, "graphs_per_s": G / t_full,
         "ms_per_step_graph_prebuilt": t_mp * 1e3, "edges_per_s_graph_prebuilt": E / t_mp,
         "ms_per_step_graph_prebuilt_hip_graph": None if t_hg is None else t_hg * 1e3,

@@ -1,4 +1,6 @@
-"""The five benchmark workloads (synthetic stand-ins for the paper's five-dataset mixture).
+"""The benchmark workloads (synthetic stand-ins for the paper's five-dataset mixture): five of growing size, and a
+sixth with the model shape the paper trains (4 layers of 866 hidden units, heads of three layers of 889 units, local
+batch of 128 structures: section "Numerical Results").
 
 Each entry restates one workload: how many graphs, how atoms are drawn, cutoff, hidden width H,
 number of message-passing layers L, GEMM operand type and number of sources S. The datasets the paper
@@ -23,6 +25,8 @@ CONFIGS = {
                  dtype="bf16", S=5, seed=0),
     "cfg5": dict(desc="4 periodic cubic cells of 20,000 atoms at 0.1 atoms/A^3", rc=6.0, H=128, L=3,
                  dtype="f32", S=1, seed=0),
+    "cfg6": dict(desc="the paper's model shape: 128 mixed 5-source structures, H=866, heads 3 x 889", rc=5.0, H=866,
+                 L=4, dtype="bf16", S=5, seed=0, Hh=889, D=3),
 }
 
 _MOL_Z2 = (1, 6, 7, 8, 9, 16)
@@ -76,12 +80,27 @@ def _gen_cfg4(rng, n_target=40000, crystal_density_cap=0.085) -> Batch:
                          meta=dict(crystal_density_cap=crystal_density_cap))
 
 
+def _gen_cfg6(rng, n_graphs=128, crystal_density_cap=0.085) -> Batch:
+    """One local batch of the paper's size, every structure drawn like those of the mixed batch of config 4."""
+    graphs, src = [], []
+    for _ in range(n_graphs):
+        s = int(rng.integers(0, 5))
+        if s <= 2:
+            graphs.append(_molecule_cfg2(rng, int(rng.integers(5, 61))))
+        else:
+            graphs.append(make_crystal(rng, int(rng.integers(8, 201)), 4.0, 15.0, 1.2, 1, 94,
+                                       max_density=crystal_density_cap))
+        src.append(s)
+    return concat_graphs(graphs, np.asarray(src, dtype=np.int32), meta=dict(crystal_density_cap=crystal_density_cap))
+
+
 def _gen_cfg5(rng, n_graphs=4, n_atoms=20000) -> Batch:
     graphs = [make_cubic_bulk(rng, n_atoms, 0.1, 1.0, 1, 30) for _ in range(n_graphs)]
     return concat_graphs(graphs)
 
 
-_GEN = {"cfg1": _gen_cfg1, "cfg2": _gen_cfg2, "cfg3": _gen_cfg3, "cfg4": _gen_cfg4, "cfg5": _gen_cfg5}
+_GEN = {"cfg1": _gen_cfg1, "cfg2": _gen_cfg2, "cfg3": _gen_cfg3, "cfg4": _gen_cfg4, "cfg5": _gen_cfg5,
+        "cfg6": _gen_cfg6}
 
 
 def make_config(name: str, seed: int | None = None, **overrides) -> tuple[Batch, dict]:

@@ -33,7 +33,7 @@ hipEvent_t get_event() {
 const char* const kNames[PT_COUNT] = {
     "neigh_setup", "neigh_count", "neigh_fill", "neigh_emit", "neigh_transpose", "pack", "gemm_node",
     "wgrad_node", "wgrad_edge", "colsum", "seg_fwd", "segsum_dst", "segsum_src", "head_out", "pool", "embed",
-    "misc", "edge_fused_fwd", "edge_fused_bwd"};
+    "misc", "edge_fused_fwd", "edge_fused_bwd", "frag_gemm_edge", "frag_wgrad_edge", "edge_elementwise", "to_frag"};
 }  // namespace
 
 void prof_record(int tag, hipStream_t st, bool start) {

@@ -288,7 +288,7 @@ int32_t launch_to_frag(hipStream_t st, const ToFragArgs& a) {
   HGNN_REQUIRE(a.Mp % 256 == 0 && a.Cp % 32 == 0, HGNN_ERR_BAD_SHAPE, "to_frag: padded extents do not tile");
   const long n = (long)(a.Mp / 8) * (a.Cp / 8);
   if (n == 0) return HGNN_OK;
-  ProfScope ps(PT_MISC, st);
+  ProfScope ps(PT_TO_FRAG, st);
   k_to_frag<<<dim3((unsigned)((n + 255) / 256), a.grp_ptr ? a.S : 1), 256, 0, st>>>(a);
   HGNN_LAUNCH_CHECK("k_to_frag");
   return HGNN_OK;
@@ -934,13 +934,13 @@ int32_t wide_layer_fwd(hipStream_t st, const WideLayerArgs& a) {
   e.a1_R = s.a1_R; e.a1_T = s.a1_T;
   if (d.Ep > 0) {
     {
-      ProfScope ps(PT_EDGE_FUSED_FWD, st);
+      ProfScope ps(PT_EDGE_ELEM, st);
       const long n = e.nrs * (Hp / 8);
       k_edge_a1<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(e);
       HGNN_LAUNCH_CHECK("k_edge_a1");
     }
     // z2 = a1 W2 + b2 (T fragments)
-    FGemmArgs g = nn_args(s.a1_R, d.nkb, (int)(d.Ep / 32), w.packed + 2 * PP, d.ncb, PT_EDGE_FUSED_FWD);
+    FGemmArgs g = nn_args(s.a1_R, d.nkb, (int)(d.Ep / 32), w.packed + 2 * PP, d.ncb, PT_FRAG_GEMM_EDGE);
     g.T = s.z2_T; g.t_ncb = d.ncb;
     g.bias = W + o.b2; g.nbias = H;
     HGNN_TRY((launch_fgemm_t<4, 2, EPI_T>(st, g)));
@@ -1062,7 +1062,7 @@ int32_t wide_layer_bwd(hipStream_t st, const WideLayerArgs& a) {
   const size_t esh = (size_t)eb.y * 2 * Hp * sizeof(float);
   HGNN_TRY(launch_edge_cvec(st, d.E, a.dst, a.rvec, a.g_v_out, a.alpha, w.cvec));
   {
-    ProfScope ps(PT_EDGE_FUSED_BWD, st);
+    ProfScope ps(PT_EDGE_ELEM, st);
     k_edge_gz2<<<eg, eb, esh, st>>>(e);
     HGNN_LAUNCH_CHECK("k_edge_gz2");
   }
@@ -1070,14 +1070,14 @@ int32_t wide_layer_bwd(hipStream_t st, const WideLayerArgs& a) {
   HGNN_TRY(launch_reduce_cols(st, w.colpart + Hp, eg, 2 * Hp, H, gW + o.wx));
   // g_W2 = a1^T g_z2
   HGNN_TRY(wgrad_w(st, d, s.a1_T, d.ncb, 0, d.ncb, w.gz2_T, d.ncb, 0, d.ncb, d.Ep, w.partial, w.partial_floats,
-                   gW + o.W2, 0, 0, PT_WGRAD_EDGE));
+                   gW + o.W2, 0, 0, PT_FRAG_WGRAD_EDGE));
   if (d.Ep > 0) {  // g_a1 = g_z2 W2^T (T fragments)
-    FGemmArgs g = nn_args(w.gz2_R, d.nkb, (int)(d.Ep / 32), w.packed + 3 * PP, d.ncb, PT_EDGE_FUSED_BWD);
+    FGemmArgs g = nn_args(w.gz2_R, d.nkb, (int)(d.Ep / 32), w.packed + 3 * PP, d.ncb, PT_FRAG_GEMM_EDGE);
     g.T = w.ga1_T; g.t_ncb = d.ncb;
     HGNN_TRY((launch_fgemm_t<4, 2, EPI_T>(st, g)));
   }
   {
-    ProfScope ps(PT_EDGE_FUSED_BWD, st);
+    ProfScope ps(PT_EDGE_ELEM, st);
     k_edge_gz1<<<eg, eb, esh, st>>>(e);
     HGNN_LAUNCH_CHECK("k_edge_gz1");
   }

@@ -4,8 +4,8 @@ from __future__ import annotations
 import numpy as np
 
 import oracle
-from hgnn_inputs import (init_embedding, init_head_weights, init_layer_weights, make_config,
-                         upstream_grads)
+from hgnn_inputs import (init_deep_head_weights, init_embedding, init_head_weights, init_layer_weights,
+                         make_config, upstream_grads)
 
 TOL = {  # norm-wise L-inf relative error (max|a-b| / max|b|) against the float64 oracle
     "f32": dict(fwd=1e-5, grad=1e-4),
@@ -24,26 +24,30 @@ def relerr(a, b):
     return float(num / den) if den > 0 else float(num)
 
 
-def make_weights(seed, H, L, S, N, G):
+def make_weights(seed, H, L, S, N, G, Hh=None, D=None):
+    """Hh, D: head width and hidden layers per head (None: the plain heads, one hidden layer of width H)."""
     ss = np.random.SeedSequence(seed).spawn(3)
     rw = np.random.default_rng(ss[1])
     rg = np.random.default_rng(ss[2])
     emb = init_embedding(rw, H)
     Ws = [init_layer_weights(rw, H) for _ in range(L)]
-    Wh = init_head_weights(rw, H, H, S)
+    Wh = init_head_weights(rw, H, H, S) if D is None else init_deep_head_weights(rw, H, Hh, D, S)
     gE, gF = upstream_grads(rg, G, N)
     return emb, Ws, Wh, gE, gF
 
 
 def problem_from_config(name, **over):
     batch, hp = make_config(name, **over)
-    emb, Ws, Wh, gE, gF = make_weights(hp["seed"], hp["H"], hp["L"], hp["S"], batch.N, batch.G)
+    emb, Ws, Wh, gE, gF = make_weights(hp["seed"], hp["H"], hp["L"], hp["S"], batch.N, batch.G, hp.get("Hh"),
+                                       hp.get("D"))
     return dict(batch=batch, hp=hp, emb=emb, Ws=Ws, Wh=Wh, gE=gE, gF=gF)
 
 
-def problem_from_batch(batch, rc, H, L, S, dtype, seed=0):
-    emb, Ws, Wh, gE, gF = make_weights(seed, H, L, S, batch.N, batch.G)
+def problem_from_batch(batch, rc, H, L, S, dtype, seed=0, Hh=None, D=None):
+    emb, Ws, Wh, gE, gF = make_weights(seed, H, L, S, batch.N, batch.G, Hh, D)
     hp = dict(rc=rc, H=H, L=L, S=S, dtype=dtype, seed=seed, name="custom")
+    if D is not None:
+        hp.update(Hh=Hh, D=D)
     return dict(batch=batch, hp=hp, emb=emb, Ws=Ws, Wh=Wh, gE=gE, gF=gF)
 
 
@@ -56,15 +60,16 @@ def oracle_step(P, graph, alpha, grads=True, keep_layers=False):
     b, hp = P["batch"], P["hp"]
     return oracle.step_fwd_bwd(b.Z, b.graph_off, b.source_id, graph, P["emb"].astype(np.float64),
                                [w.astype(np.float64) for w in P["Ws"]], P["Wh"].astype(np.float64),
-                               hp["H"], hp["S"], alpha,
+                               hp.get("Hh", hp["H"]), hp["S"], alpha,
                                P["gE"].astype(np.float64) if grads else None,
-                               P["gF"].astype(np.float64) if grads else None, keep_layers=keep_layers)
+                               P["gF"].astype(np.float64) if grads else None, keep_layers=keep_layers, D=hp.get("D"))
 
 
 def gpu_hotpath(P, alpha=None):
     from paper_2506_21788_amd.step import HotPath
     b, hp = P["batch"], P["hp"]
-    return HotPath(b, hp["rc"], hp["H"], hp["L"], hp["S"], hp["dtype"], P["emb"], P["Ws"], P["Wh"], alpha=alpha)
+    return HotPath(b, hp["rc"], hp["H"], hp["L"], hp["S"], hp["dtype"], P["emb"], P["Ws"], P["Wh"], alpha=alpha,
+                   Hh=hp.get("Hh"), D=hp.get("D"))
 
 
 def assert_graph_equal(got, want):

@@ -416,3 +416,46 @@ def test_reduced_cfg5_backward():
     b = concat_graphs(graphs)
     P = problem_from_batch(b, 6.0, 128, 3, 1, "f32", seed=3)
     compare_step(P, "cfg5-reduced")
+
+
+# ------------------------------------------------------------------------------------------------
+# the paper's model shape: 866 hidden units, heads of three layers of 889 units (fragment-GEMM path)
+# ------------------------------------------------------------------------------------------------
+def test_step_small_mixed_paper_shape():
+    say("step small mixed, H = 866, heads 3 x 889")
+    b = small_mixed_batch(11, n_mol=5, n_cry=4, S=3, mol_atoms=(3, 40), cry_atoms=(2, 30))
+    P = problem_from_batch(b, 4.5, 866, 2, 3, "bf16", seed=866, Hh=889, D=3)
+    compare_step(P, "small H=866 Hh=889 D=3 bf16")
+
+
+def test_full_size_cfg6_sampled_graphs():
+    """Config 6 (128 structures, ~8k atoms, ~250k edges, H = 866, 4 layers, heads 3 x 889). A graph's outputs depend
+    on that graph only, so the oracle recomputes sampled graphs as a batch of their own."""
+    say("cfg6 full size")
+    import torch
+    P = problem_from_config("cfg6")
+    b, hp = P["batch"], P["hp"]
+    hpth = gpu_hotpath(P)
+    hpth.build_graph()
+    hpth.forward()
+    hpth.backward(torch.as_tensor(P["gE"]).cuda(), torch.as_tensor(P["gF"]).cuda())
+    torch.cuda.synchronize()
+    say("cfg6 N", b.N, "G", b.G, "E", hpth.graph.E, "alpha", hpth.alpha)
+    rng = np.random.default_rng(6)
+    graphs = np.sort(rng.choice(b.G, size=6, replace=False))
+    sb = sub_batch(b, graphs)
+    atoms = np.concatenate([np.arange(b.graph_off[g], b.graph_off[g + 1]) for g in graphs])
+    Ps = dict(P, batch=sb, gE=P["gE"][graphs], gF=P["gF"][atoms])
+    og = oracle_graph(Ps)
+    say("cfg6 sample: atoms", sb.N, "edges", og["E"])
+    want = oracle_step(Ps, og, hpth.alpha)
+    tol = TOL["bf16"]
+    errs = dict(energy=relerr(hpth.energy.cpu().numpy()[graphs], want["energy"]),
+                force=relerr(hpth.force.cpu().numpy()[atoms], want["force"]),
+                h=relerr(hpth.h[-1].cpu().numpy()[atoms], want["h"]),
+                g_h0=relerr(hpth.g_h0.cpu().numpy()[atoms], want["g_h0"]))
+    say("cfg6 sampled", {k: f"{v:.2e}" for k, v in errs.items()})
+    assert errs["energy"] <= tol["fwd"] and errs["force"] <= tol["fwd"] and errs["h"] <= tol["fwd"]
+    assert errs["g_h0"] <= tol["grad"]
+    for t in (hpth.gWhead, hpth.g_emb, *hpth.gW):
+        assert bool(torch.isfinite(t).all())
