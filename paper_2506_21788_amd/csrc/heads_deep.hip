@@ -174,7 +174,7 @@ static DeepWs carve_deep_ws(void* p, const DeepDims& d) {
   w.gzD[0] = c.take<float>((size_t)d.G * d.Hhp + 4);
   w.gzD[1] = c.take<float>((size_t)d.N * d.Hhp + 4);
   w.gq = c.take<float>((size_t)d.N + 1);
-  w.partial_floats = (size_t)4 * d.S * d.Pmax * d.Pmax;
+  w.partial_floats = (size_t)8 * d.S * d.Pmax * d.Pmax;
   w.partial = c.take<float>(w.partial_floats);
   w.cs_partial = c.take<float>(colsum_rows_partial_floats(M, d.Hhp, d.S));
   w.bytes = c.used();

@@ -46,18 +46,35 @@ struct FCfg {
   static_assert(NF % 4 == 0, "fragments per step must divide among four wavefronts");
 };
 
+typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
+
 template <int WI, int WJ, int EPI>
 __global__ void __launch_bounds__(256, (WI * WJ <= 8 ? 2 : 1)) k_fgemm(FGemmArgs p) {
   using C = FCfg<WI, WJ>;
-  extern __shared__ __align__(16) uint4 lds[];
+  extern __shared__ __align__(16) u32x4_t lds[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wi = wave >> 1, wj = wave & 1;
-  int i0 = blockIdx.y * C::TI;
-  const int j0 = blockIdx.x * C::TJ;
-  // blockIdx.z: (group, split) for split partials, else the group
-  const int grp = EPI == EPI_PART ? blockIdx.z / p.nsplit : blockIdx.z;
-  const int split = EPI == EPI_PART ? blockIdx.z % p.nsplit : 0;
+  // Workgroups go to the 8 XCDs round-robin by blockIdx.x, and each XCD has its own L2. Workgroups that read the
+  // same operand panel are therefore given ids of the same residue mod 8, next to each other in that XCD's order:
+  // row products: the column tiles of one row tile; split partials: all tiles of one split. blockIdx.z: group.
+  const int xcd = blockIdx.x & 7, q = blockIdx.x >> 3;
+  const int nTj = p.nJ / C::TJ;
+  int ti, tj, split = 0;
+  if (EPI == EPI_PART) {
+    const int tiles = (p.nI / C::TI) * nTj;
+    const int t = q % tiles;
+    split = (q / tiles) * 8 + xcd;     // the launcher makes the split count a multiple of 8
+    ti = t / nTj;
+    tj = t % nTj;
+  } else {
+    ti = (q / nTj) * 8 + xcd;
+    tj = q % nTj;
+    if (ti >= p.nI / C::TI) return;    // uniform over the workgroup, before any barrier
+  }
+  int i0 = ti * C::TI;
+  const int j0 = tj * C::TJ;
+  const int grp = blockIdx.z;
   int mvalid = p.M, pos0 = 0, pad0 = 0, kbase = 0, knum = p.nkb;
   if (p.grp_ptr) {
     int n;
@@ -67,7 +84,7 @@ __global__ void __launch_bounds__(256, (WI * WJ <= 8 ? 2 : 1)) k_fgemm(FGemmArgs
       kbase = pad0 / 16;
       knum = npad / 16;
     } else {
-      if ((int)blockIdx.y * C::TI * 32 >= npad) return;   // uniform over the workgroup, before any barrier
+      if (ti * C::TI * 32 >= npad) return;   // uniform over the workgroup, before any barrier
       i0 += pad0 / 32;
       mvalid = pad0 + n;
     }
@@ -93,11 +110,7 @@ __global__ void __launch_bounds__(256, (WI * WJ <= 8 ? 2 : 1)) k_fgemm(FGemmArgs
       kst[s] = p.b_sk * 1024;
     }
   }
-  uint4 pre[C::PASSES];
-  auto fetch = [&](int kb) {
-#pragma unroll
-    for (int s = 0; s < C::PASSES; ++s) pre[s] = *reinterpret_cast<const uint4*>(src[s] + (long)kb * kst[s]);
-  };
+  u32x4_t pre[C::PASSES];
 
   f32x16_t acc[WI][WJ];
 #pragma unroll
@@ -107,25 +120,32 @@ __global__ void __launch_bounds__(256, (WI * WJ <= 8 ? 2 : 1)) k_fgemm(FGemmArgs
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  if (kbeg < kend) fetch(kbeg);
+  // (loads are unconditional, from a clamped step: the staging registers must stay registers)
+  {
+    const int k0 = kbeg < kend ? kbeg : 0;
+#pragma unroll
+    for (int s = 0; s < C::PASSES; ++s) pre[s] = *reinterpret_cast<const u32x4_t*>(src[s] + (long)k0 * kst[s]);
+  }
   for (int kb = kbeg; kb < kend; kb += C::KC) {
     __syncthreads();   // the previous step's fragments have been consumed
 #pragma unroll
     for (int s = 0; s < C::PASSES; ++s) lds[(4 * s + wave) * 64 + lane] = pre[s];
     __syncthreads();
-    if (kb + C::KC < kend) fetch(kb + C::KC);   // the next step travels during the products
+    {  // the next step travels during the products (the last step loads itself again)
+      const int kn = kb + C::KC < kend ? kb + C::KC : kb;
+#pragma unroll
+      for (int s = 0; s < C::PASSES; ++s) pre[s] = *reinterpret_cast<const u32x4_t*>(src[s] + (long)kn * kst[s]);
+    }
 #pragma unroll
     for (int kk = 0; kk < C::KC; ++kk) {
       bf16x8_t a[WI], b[WJ];
 #pragma unroll
       for (int i = 0; i < WI; ++i) {
-        const uint4 w = lds[(kk * C::TI + wi * WI + i) * 64 + lane];
-        a[i] = *reinterpret_cast<const bf16x8_t*>(&w);
+        a[i] = __builtin_bit_cast(bf16x8_t, lds[(kk * C::TI + wi * WI + i) * 64 + lane]);
       }
 #pragma unroll
       for (int j = 0; j < WJ; ++j) {
-        const uint4 w = lds[(C::KC * C::TI + kk * C::TJ + wj * WJ + j) * 64 + lane];
-        b[j] = *reinterpret_cast<const bf16x8_t*>(&w);
+        b[j] = __builtin_bit_cast(bf16x8_t, lds[(C::KC * C::TI + kk * C::TJ + wj * WJ + j) * 64 + lane]);
       }
 #pragma unroll
       for (int i = 0; i < WI; ++i)
@@ -171,7 +191,7 @@ __global__ void __launch_bounds__(256, (WI * WJ <= 8 ? 2 : 1)) k_fgemm(FGemmArgs
           }
         }
       } else {
-        float* out = p.P + (long)blockIdx.z * p.split_stride;   // [group][split]
+        float* out = p.P + ((long)grp * p.nsplit + split) * p.split_stride;   // [group][split]
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
           const int row = ib * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
@@ -188,13 +208,14 @@ static int32_t launch_fgemm_t(hipStream_t st, const FGemmArgs& a) {
   HGNN_REQUIRE(a.nI % C::TI == 0 && a.nJ % C::TJ == 0 && a.nkb % C::KC == 0 && a.kper % C::KC == 0 && a.kper > 0,
                HGNN_ERR_BAD_SHAPE, "fragment GEMM: %d x %d blocks, %d contraction blocks do not tile", a.nI, a.nJ, a.nkb);
   if (a.nI == 0 || a.nJ == 0) return HGNN_OK;
-  const int nsplit = a.nkb == 0 ? 1 : (a.nkb + a.kper - 1) / a.kper;
-  HGNN_REQUIRE(nsplit == a.nsplit && (EPI == EPI_PART || nsplit == 1), HGNN_ERR_BAD_SHAPE,
-               "fragment GEMM: split count mismatch");
+  HGNN_REQUIRE(EPI == EPI_PART ? (a.nsplit % 8 == 0 && (long)a.nsplit * a.kper >= a.nkb) : (a.nsplit == 1 && a.kper == a.nkb),
+               HGNN_ERR_BAD_SHAPE, "fragment GEMM: bad split of the contraction");
   const int groups = a.grp_ptr ? a.S : 1;
-  HGNN_REQUIRE(a.nI / C::TI <= 65535 && (long)nsplit * groups <= 65535, HGNN_ERR_OVERFLOW, "fragment GEMM: grid too large");
+  const long nTi = a.nI / C::TI, nTj = a.nJ / C::TJ;
+  const long gx = EPI == EPI_PART ? (long)a.nsplit * nTi * nTj : (nTi + 7) / 8 * 8 * nTj;
+  HGNN_REQUIRE(gx <= 2147483647L && groups <= 65535, HGNN_ERR_OVERFLOW, "fragment GEMM: grid too large");
   ProfScope ps(a.tag, st);
-  k_fgemm<WI, WJ, EPI><<<dim3(a.nJ / C::TJ, a.nI / C::TI, nsplit * groups), 256, C::LDS_BYTES, st>>>(a);
+  k_fgemm<WI, WJ, EPI><<<dim3((unsigned)gx, 1, groups), 256, C::LDS_BYTES, st>>>(a);
   HGNN_LAUNCH_CHECK("k_fgemm");
   return HGNN_OK;
 }
@@ -842,12 +863,14 @@ int32_t launch_fwgrad(hipStream_t st, const FWgradArgs& a) {
   const long cap = (long)(a.partial_floats / ((size_t)a.nI * 32 * a.nJ * 32 * groups));
   if (want > cap) want = cap;
   if (want > WIDE_MAX_SPLITS) want = WIDE_MAX_SPLITS;
-  if (want < 1) want = 1;
+  want = want / 8 * 8;   // a multiple of 8: one XCD per residue (see k_fgemm)
+  if (want < 8) want = 8;
+  HGNN_REQUIRE(cap >= 8, HGNN_ERR_WORKSPACE_TOO_SMALL, "weight-gradient partials do not fit the workspace");
   int kper = (int)((g.nkb + want - 1) / want);
   kper = (kper + 1) / 2 * 2;
   if (kper < 2) kper = 2;
   g.kper = kper;
-  g.nsplit = g.nkb == 0 ? 1 : (g.nkb + kper - 1) / kper;
+  g.nsplit = (int)want;   // splits past the end of the rows write zeros
   g.P = a.partial; g.ldp = (long)a.nJ * 32; g.split_stride = (long)a.nI * 32 * a.nJ * 32;
   g.tag = a.tag;
   HGNN_REQUIRE((size_t)g.nsplit * groups * g.split_stride <= a.partial_floats, HGNN_ERR_WORKSPACE_TOO_SMALL,
