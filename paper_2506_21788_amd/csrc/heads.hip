@@ -146,30 +146,60 @@ __global__ void k_embed_fwd_any(int N, int H, const int32_t* __restrict__ Z, con
   h[idx] = emb[(long)z * H + c];
 }
 
-// block (z, chunk), thread = column (strided): atoms of the chunk with Z == z in ascending order
+// block (z, chunk): the atoms of the chunk with Z == z are listed in ascending order (each thread scans 8 consecutive
+// atoms, an exclusive scan over the threads places its matches), then every column is summed over that list
 __global__ void __launch_bounds__(256)
 k_embed_bwd_part_any(int N, int H, const int32_t* __restrict__ Z, const float* __restrict__ g_h,
                      float* __restrict__ part /*[nchunk][ZMAX+1][H]*/) {
-  const int z = blockIdx.x, chunk = blockIdx.y;
+  static_assert(EMB_CHUNK == 2048, "8 atoms per thread");
+  __shared__ int list[EMB_CHUNK];
+  __shared__ int cnt[257];
+  const int z = blockIdx.x, chunk = blockIdx.y, tid = threadIdx.x;
   const int lo = chunk * EMB_CHUNK;
   const int hi = lo + EMB_CHUNK < N ? lo + EMB_CHUNK : N;
-  for (int c = threadIdx.x; c < H; c += 256) {
+  bool m[8];
+  int n = 0;
+#pragma unroll
+  for (int u = 0; u < 8; ++u) {
+    const int i = lo + tid * 8 + u;
+    m[u] = i < hi && Z[i] == z;
+    n += m[u] ? 1 : 0;
+  }
+  cnt[tid + 1] = n;
+  if (tid == 0) cnt[0] = 0;
+  __syncthreads();
+  if (tid == 0)
+    for (int k = 1; k <= 256; ++k) cnt[k] += cnt[k - 1];
+  __syncthreads();
+  int o = cnt[tid];
+#pragma unroll
+  for (int u = 0; u < 8; ++u)
+    if (m[u]) list[o++] = lo + tid * 8 + u;
+  __syncthreads();
+  const int total = cnt[256];
+  for (int c = tid; c < H; c += 256) {
     float acc = 0.f;
-    for (int i = lo; i < hi; ++i)
-      if (Z[i] == z) acc += g_h[(size_t)i * H + c];
+    for (int k = 0; k < total; ++k) acc += g_h[(size_t)list[k] * H + c];
     part[((size_t)chunk * (HGNN_ZMAX + 1) + z) * H + c] = acc;
   }
 }
 
+// block (graph, 64-column slab): 4 row phases take every fourth atom, then the phases are added in order
 __global__ void __launch_bounds__(256)
 k_pool_fwd_any(int H, int mode, const int32_t* __restrict__ graph_off, const float* __restrict__ h, float* __restrict__ p) {
+  __shared__ float sh[4][64];
   const int g = blockIdx.x;
+  const int cl = threadIdx.x & 63, ph = threadIdx.x >> 6;
+  const int c = blockIdx.y * 64 + cl;
   const int lo = graph_off[g], hi = graph_off[g + 1];
-  const float sc = (mode == HGNN_POOL_MEAN && hi > lo) ? 1.0f / (float)(hi - lo) : 1.0f;
-  for (int c = threadIdx.x; c < H; c += 256) {
-    float acc = 0.f;
-    for (int i = lo; i < hi; ++i) acc += h[(size_t)i * H + c];
-    p[(size_t)g * H + c] = acc * sc;
+  float acc = 0.f;
+  if (c < H)
+    for (int i = lo + ph; i < hi; i += 4) acc += h[(size_t)i * H + c];
+  sh[ph][cl] = acc;
+  __syncthreads();
+  if (ph == 0 && c < H) {
+    const float sc = (mode == HGNN_POOL_MEAN && hi > lo) ? 1.0f / (float)(hi - lo) : 1.0f;
+    p[(size_t)g * H + c] = (((sh[0][cl] + sh[1][cl]) + sh[2][cl]) + sh[3][cl]) * sc;
   }
 }
 
@@ -451,7 +481,7 @@ extern "C" int32_t hgnn_pool_by_graph_fwd(void* stream, int32_t N, int32_t G, in
   HGNN_REQUIRE(graph_off && p && (h || N == 0), HGNN_ERR_NULLPTR, "pool_fwd: null pointer");
   ProfScope ps(PT_POOL, st);
   if (valid_H(H)) k_pool_fwd<<<G, 1024, 0, st>>>(H, mode, graph_off, h, p);
-  else k_pool_fwd_any<<<G, 256, 0, st>>>(H, mode, graph_off, h, p);
+  else k_pool_fwd_any<<<dim3(G, (H + 63) / 64), 256, 0, st>>>(H, mode, graph_off, h, p);
   HGNN_LAUNCH_CHECK("k_pool_fwd");
   return HGNN_OK;
 }

@@ -248,6 +248,8 @@ int32_t launch_pack_frag(hipStream_t st, const PackFragArgs& a) {
 // ---------------------------------------------------------------------------------------------
 // row-major fp32 -> fragments.  mode 0: x, 1: silu(x), 2: x * silu'(z)
 // ---------------------------------------------------------------------------------------------
+// VEC: floats per load (the launcher picks 4 / 2 / 1 from the alignment of the sources)
+template <int VEC>
 __global__ void __launch_bounds__(256) k_to_frag(ToFragArgs a) {
   const int CG = a.Cp >> 3;
   const long idx = (long)blockIdx.x * 256 + threadIdx.x;
@@ -266,15 +268,31 @@ __global__ void __launch_bounds__(256) k_to_frag(ToFragArgs a) {
   for (int u = 0; u < 8; ++u) {
     const int r = tset_row((int)(rs >> 1), g, u);
     const long sr = r < n ? (a.row_idx ? a.row_idx[pos0 + r] : pad0 + r) : 0;
+    typedef float vec_t __attribute__((ext_vector_type(VEC)));
 #pragma unroll
-    for (int k = 0; k < 8; ++k) {
-      float v = 0.f;
-      if (r < n && c0 + k < a.ncol) {
-        v = a.X[sr * a.ldx + c0 + k];
-        if (a.mode == 1) v = silu_f(v);
-        else if (a.mode == 2) v *= dsilu_f(a.Z[sr * a.ldz + c0 + k]);
+    for (int k = 0; k < 8; k += VEC) {
+      float xv[VEC], zv[VEC];
+#pragma unroll
+      for (int t = 0; t < VEC; ++t) { xv[t] = 0.f; zv[t] = 0.f; }
+      // a whole vector is read where the row pitch covers it; single columns past ncol are zeroed below
+      if (r < n && c0 + k + VEC <= a.ldx && c0 + k < a.ncol) {
+        const vec_t x = *reinterpret_cast<const vec_t*>(a.X + sr * a.ldx + c0 + k);
+#pragma unroll
+        for (int t = 0; t < VEC; ++t) xv[t] = x[t];
+        if (a.mode == 2) {
+          const vec_t zz = *reinterpret_cast<const vec_t*>(a.Z + sr * a.ldz + c0 + k);
+#pragma unroll
+          for (int t = 0; t < VEC; ++t) zv[t] = zz[t];
+        }
       }
-      vals[u][k] = (unsigned short)f2bf_bits(v);
+#pragma unroll
+      for (int t = 0; t < VEC; ++t) {
+        float v = xv[t];
+        if (a.mode == 1) v = silu_f(v);
+        else if (a.mode == 2) v *= dsilu_f(zv[t]);
+        if (c0 + k + t >= a.ncol) v = 0.f;
+        vals[u][k + t] = (unsigned short)f2bf_bits(v);
+      }
     }
   }
   const int rb16 = (int)(rs >> 1) + pad0 / 16;   // destination rows are the padded ones
@@ -310,7 +328,16 @@ int32_t launch_to_frag(hipStream_t st, const ToFragArgs& a) {
   const long n = (long)(a.Mp / 8) * (a.Cp / 8);
   if (n == 0) return HGNN_OK;
   ProfScope ps(PT_TO_FRAG, st);
-  k_to_frag<<<dim3((unsigned)((n + 255) / 256), a.grp_ptr ? a.S : 1), 256, 0, st>>>(a);
+  const dim3 grid((unsigned)((n + 255) / 256), a.grp_ptr ? a.S : 1);
+  auto fits = [&](int vec) {
+    const auto ok = [&](const float* p, long ld) {
+      return p == nullptr || (reinterpret_cast<uintptr_t>(p) % (4 * vec) == 0 && ld % vec == 0);
+    };
+    return ok(a.X, a.ldx) && (a.mode != 2 || ok(a.Z, a.ldz));
+  };
+  if (fits(4)) k_to_frag<4><<<grid, 256, 0, st>>>(a);
+  else if (fits(2)) k_to_frag<2><<<grid, 256, 0, st>>>(a);
+  else k_to_frag<1><<<grid, 256, 0, st>>>(a);
   HGNN_LAUNCH_CHECK("k_to_frag");
   return HGNN_OK;
 }
@@ -318,21 +345,43 @@ int32_t launch_to_frag(hipStream_t st, const ToFragArgs& a) {
 // ---------------------------------------------------------------------------------------------
 // column sums of small row-major tensors and ordered reduction of per-block partial rows
 // ---------------------------------------------------------------------------------------------
-// dest[c] = sum over s < nsplit (ascending) of partial[s * stride + c], c < ncol   (blockIdx.y: group)
-__global__ void __launch_bounds__(256) k_reduce_cols(const float* __restrict__ partial, int nsplit, long stride,
-                                                     int ncol, float* __restrict__ dest, long partial_grp_stride,
-                                                     long dest_grp_stride) {
-  const int c = blockIdx.x * 256 + threadIdx.x;
-  if (c >= ncol) return;
-  const float* p = partial + blockIdx.y * partial_grp_stride;
+// dest[c] = sum over s < nsplit of partial[s * stride + c], c < ncol   (blockIdx.y: group). Fixed order: 16 row
+// phases each sum a contiguous run of partials in ascending order, then the phases are added in ascending order.
+__global__ void __launch_bounds__(1024) k_reduce_cols(const float* __restrict__ partial, int nsplit, long stride,
+                                                      int ncol, float* __restrict__ dest, long partial_grp_stride,
+                                                      long dest_grp_stride) {
+  __shared__ float sh[16][64];
+  const int cl = threadIdx.x & 63, ph = threadIdx.x >> 6;
+  const int c = blockIdx.x * 64 + cl;
+  const int per = (nsplit + 15) / 16;
+  const int k0 = ph * per;
+  const int k1 = k0 + per < nsplit ? k0 + per : nsplit;
   float s = 0.f;
-  for (int k = 0; k < nsplit; ++k) s += p[(long)k * stride + c];
-  dest[blockIdx.y * dest_grp_stride + c] = s;
+  if (c < ncol) {
+    const float* p = partial + blockIdx.y * partial_grp_stride + c;
+    int k = k0;
+    for (; k + 8 <= k1; k += 8) {
+      float v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = p[(long)(k + u) * stride];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) s += v[u];
+    }
+    for (; k < k1; ++k) s += p[(long)k * stride];
+  }
+  sh[ph][cl] = s;
+  __syncthreads();
+  if (ph == 0 && c < ncol) {
+    float t = sh[0][cl];
+#pragma unroll
+    for (int q = 1; q < 16; ++q) t += sh[q][cl];
+    dest[blockIdx.y * dest_grp_stride + c] = t;
+  }
 }
 static int32_t launch_reduce_cols(hipStream_t st, const float* partial, int nsplit, long stride, int ncol, float* dest,
                                   int groups = 1, long partial_grp_stride = 0, long dest_grp_stride = 0) {
-  k_reduce_cols<<<dim3((ncol + 255) / 256, groups), 256, 0, st>>>(partial, nsplit, stride, ncol, dest, partial_grp_stride,
-                                                                  dest_grp_stride);
+  k_reduce_cols<<<dim3((ncol + 63) / 64, groups), 1024, 0, st>>>(partial, nsplit, stride, ncol, dest, partial_grp_stride,
+                                                                 dest_grp_stride);
   HGNN_LAUNCH_CHECK("k_reduce_cols");
   return HGNN_OK;
 }
@@ -412,6 +461,7 @@ struct EdgeElemArgs {
   char* gz2_R = nullptr;
   char* gz2_T = nullptr;
   char* ga1_T = nullptr;                // g_a1 in, g_z1 out (in place)
+  unsigned short* gz1_rm = nullptr;     // g_z1 again, bf16 row-major [rows, Hp]: what the source-sorted sum gathers
   float* colpart = nullptr;             // [blocks][2][Hp] column-sum partials
 };
 
@@ -584,6 +634,9 @@ __global__ void __launch_bounds__(256) k_edge_gz1(EdgeElemArgs p) {
       }
     }
     store_T(p.ga1_T, p.Hp / 32, rb16, g, c0, ga);
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      *reinterpret_cast<uint4*>(p.gz1_rm + (long)tset_row(rb16, g, u) * p.Hp + c0) = pack8(ga[u]);
   }
   write_colpart(sh, p.colpart, p.Hp, s0, s1);
 }
@@ -703,6 +756,62 @@ __global__ void __launch_bounds__(256) k_segsum_w(int N, const int32_t* __restri
   for (int cb = 0; cb < NCB; ++cb) {
     const float t = acc[cb] + __shfl_xor(acc[cb], 32);
     if (g == 0) out[(long)i * ldo + cb * 32 + x] = t;
+  }
+}
+
+// out[i][c] = sum over k in ptr[i] .. ptr[i+1] of X[perm[k]][c], X bf16 row-major with pitch Hp (one wavefront per
+// atom, 16-byte pieces of a row per lane, two rows in flight)
+__global__ void __launch_bounds__(256) k_segsum_rows(int N, int Hp, const int32_t* __restrict__ ptr,
+                                                     const int32_t* __restrict__ perm, const unsigned short* __restrict__ X,
+                                                     float* __restrict__ out, long ldo) {
+  const int lane = threadIdx.x & 63;
+  const int i = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (i >= N) return;
+  const int e0 = ptr[i], e1 = ptr[i + 1];
+  const int nch = Hp >> 3;                 // 16-byte pieces per row (at most 128)
+  const bool two = lane + 64 < nch;
+  float a0[8] = {}, a1[8] = {};
+  const uint4 zero = make_uint4(0u, 0u, 0u, 0u);
+  int k = e0;
+  for (; k + 2 <= e1; k += 2) {
+    const unsigned short* r0 = X + (long)perm[k] * Hp;
+    const unsigned short* r1 = X + (long)perm[k + 1] * Hp;
+    const uint4 w00 = *reinterpret_cast<const uint4*>(r0 + lane * 8);
+    const uint4 w10 = *reinterpret_cast<const uint4*>(r1 + lane * 8);
+    const uint4 w01 = two ? *reinterpret_cast<const uint4*>(r0 + (lane + 64) * 8) : zero;
+    const uint4 w11 = two ? *reinterpret_cast<const uint4*>(r1 + (lane + 64) * 8) : zero;
+    float f[8];
+    unpack8(w00, f);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) a0[u] += f[u];
+    unpack8(w10, f);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) a0[u] += f[u];
+    unpack8(w01, f);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) a1[u] += f[u];
+    unpack8(w11, f);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) a1[u] += f[u];
+  }
+  if (k < e1) {
+    const unsigned short* r0 = X + (long)perm[k] * Hp;
+    float f[8];
+    unpack8(*reinterpret_cast<const uint4*>(r0 + lane * 8), f);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) a0[u] += f[u];
+    unpack8(two ? *reinterpret_cast<const uint4*>(r0 + (lane + 64) * 8) : zero, f);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) a1[u] += f[u];
+  }
+  float* o = out + (long)i * ldo;
+  if (lane < nch) {
+    *reinterpret_cast<float4*>(o + lane * 8) = make_float4(a0[0], a0[1], a0[2], a0[3]);
+    *reinterpret_cast<float4*>(o + lane * 8 + 4) = make_float4(a0[4], a0[5], a0[6], a0[7]);
+  }
+  if (two) {
+    *reinterpret_cast<float4*>(o + (lane + 64) * 8) = make_float4(a1[0], a1[1], a1[2], a1[3]);
+    *reinterpret_cast<float4*>(o + (lane + 64) * 8 + 4) = make_float4(a1[4], a1[5], a1[6], a1[7]);
   }
 }
 
@@ -1080,6 +1189,7 @@ int32_t wide_layer_bwd(hipStream_t st, const WideLayerArgs& a) {
   e.dst = a.dst; e.col = a.col; e.d2 = a.d2; e.PQ = s.PQ; e.w1d = W + o.W1 + 2 * HH;
   e.z2_T = s.z2_T; e.gM = w.gM_b + Hp; e.ldgM = 2 * Hp; e.cvec = w.cvec; e.wx = W + o.wx; e.alpha = a.alpha;
   e.gz2_R = w.gz2_R; e.gz2_T = w.gz2_T; e.ga1_T = w.ga1_T; e.colpart = w.colpart;
+  e.gz1_rm = reinterpret_cast<unsigned short*>(w.gz2_R);   // free again once g_a1 has been formed
   const dim3 eb = elem_block(Hp);
   const int eg = elem_grid(e.nrs, Hp);
   const size_t esh = (size_t)eb.y * 2 * Hp * sizeof(float);
@@ -1089,8 +1199,11 @@ int32_t wide_layer_bwd(hipStream_t st, const WideLayerArgs& a) {
     k_edge_gz2<<<eg, eb, esh, st>>>(e);
     HGNN_LAUNCH_CHECK("k_edge_gz2");
   }
-  HGNN_TRY(launch_reduce_cols(st, w.colpart, eg, 2 * Hp, H, gW + o.b2));
-  HGNN_TRY(launch_reduce_cols(st, w.colpart + Hp, eg, 2 * Hp, H, gW + o.wx));
+  {
+    ProfScope ps(PT_COLSUM, st);
+    HGNN_TRY(launch_reduce_cols(st, w.colpart, eg, 2 * Hp, H, gW + o.b2));
+    HGNN_TRY(launch_reduce_cols(st, w.colpart + Hp, eg, 2 * Hp, H, gW + o.wx));
+  }
   // g_W2 = a1^T g_z2
   HGNN_TRY(wgrad_w(st, d, s.a1_T, d.ncb, 0, d.ncb, w.gz2_T, d.ncb, 0, d.ncb, d.Ep, w.partial, w.partial_floats,
                    gW + o.W2, 0, 0, PT_FRAG_WGRAD_EDGE));
@@ -1104,13 +1217,19 @@ int32_t wide_layer_bwd(hipStream_t st, const WideLayerArgs& a) {
     k_edge_gz1<<<eg, eb, esh, st>>>(e);
     HGNN_LAUNCH_CHECK("k_edge_gz1");
   }
-  HGNN_TRY(launch_reduce_cols(st, w.colpart, eg, 2 * Hp, H, gW + o.b1));
-  HGNN_TRY(launch_reduce_cols(st, w.colpart + Hp, eg, 2 * Hp, H, gW + o.W1 + 2 * HH));
+  {
+    ProfScope ps(PT_COLSUM, st);
+    HGNN_TRY(launch_reduce_cols(st, w.colpart, eg, 2 * Hp, H, gW + o.b1));
+    HGNN_TRY(launch_reduce_cols(st, w.colpart + Hp, eg, 2 * Hp, H, gW + o.W1 + 2 * HH));
+  }
   // g_P, g_Q: per-atom sums of g_z1 over the destination-sorted and the source-sorted lists
   HGNN_TRY(launch_seg_w(st, PT_SEGSUM_DST, false, Hp, d.N, a.row_ptr, nullptr, w.ga1_T, nullptr, nullptr, H, 0.f, nullptr,
                         w.g_PQ, 2 * Hp, nullptr));
-  HGNN_TRY(launch_seg_w(st, PT_SEGSUM_SRC, false, Hp, d.N, a.colT_ptr, a.permT, w.ga1_T, nullptr, nullptr, H, 0.f,
-                        nullptr, w.g_PQ + Hp, 2 * Hp, nullptr));
+  if (d.N > 0) {
+    ProfScope ps(PT_SEGSUM_SRC, st);
+    k_segsum_rows<<<(unsigned)((d.N + 3) / 4), 256, 0, st>>>(d.N, Hp, a.colT_ptr, a.permT, e.gz1_rm, w.g_PQ + Hp, 2 * Hp);
+    HGNN_LAUNCH_CHECK("k_segsum_rows");
+  }
   {  // [g_P | g_Q] as R (contraction 2 Hp) and T
     ToFragArgs t;
     t.X = w.g_PQ; t.ldx = 2 * Hp; t.M = d.N; t.Mp = d.Np; t.ncol = 2 * Hp; t.Cp = 2 * Hp;
