@@ -4,11 +4,12 @@
 //                  residuals (atom tensors), fp32 split partials (weight gradients)
 //   k_pack_frag    fp32 weight slices -> B fragments (zero padded)
 //   k_to_frag      row-major fp32 atom tensor -> R and / or T fragments (optionally silu(x) or x * silu'(z))
-//   k_edge_a1      a1 = silu(P[dst] + Q[col] + d2 w1d)                          -> R and T
+//   k_edge_elem    the three element-wise edge kernels on 32 x 64 tiles: a1 = silu(P[dst] + Q[col] + d2 w1d) -> R, T;
+//                  g_z2 = (alpha g_M[dst] + c_e wx) silu'(z2) -> R, T (+ column sums for g_b2, g_wx);
+//                  g_z1 = g_a1 silu'(z1) -> T in place and row-major (+ column sums for g_b1, g_w1d)
 //   k_seg_fwd_w    M_i = alpha sum silu(z2), v'_i = v_i + alpha sum (wx . m_e) rvec_e   (one wavefront per atom)
-//   k_edge_gz2     g_z2 = (alpha g_M[dst] + c_e wx) silu'(z2) -> R and T, with the column sums for g_b2, g_wx
-//   k_edge_gz1     g_z1 = g_a1 silu'(z1) in place (T), with the column sums for g_b1, g_w1d
-//   k_segsum_w     per-atom sums of g_z1 rows over the destination-sorted or source-sorted edge lists
+//   k_segsum_w     per-atom sums of g_z1 over the destination-sorted rows (T fragments)
+//   k_segsum_rows  per-atom sums of g_z1 over the source-sorted edge list (row gathers of the row-major copy)
 // The layer follows the same algebra as the narrow path: the first edge layer is split by linearity into per-atom
 // products P = h W1a + b1, Q = h W1b that the edges gather.
 #include "wide.h"
@@ -19,6 +20,8 @@
 #include "edgeops.h"
 
 namespace hgnn {
+
+typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
 
 // row of slot u of lane half g in the 16-row group rb16 (the accumulator layout of the 32x32 matrix-core tile)
 __device__ __forceinline__ int tset_row(int rb16, int g, int u) { return rb16 * 16 + 8 * (u >> 2) + 4 * g + (u & 3); }
@@ -42,11 +45,9 @@ struct FCfg {
   static constexpr int TI = 2 * WI, TJ = 2 * WJ;
   static constexpr int NF = KC * (TI + TJ);  // fragments per step
   static constexpr int PASSES = NF / 4;      // each wavefront copies one fragment per pass
-  static constexpr int LDS_BYTES = NF * 1024;
+  static constexpr int LDS_BYTES = 3 * NF * 1024;   // a ring of three steps
   static_assert(NF % 4 == 0, "fragments per step must divide among four wavefronts");
 };
-
-typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
 
 template <int WI, int WJ, int EPI>
 __global__ void __launch_bounds__(256, (WI * WJ <= 8 ? 2 : 1)) k_fgemm(FGemmArgs p) {
@@ -110,8 +111,6 @@ __global__ void __launch_bounds__(256, (WI * WJ <= 8 ? 2 : 1)) k_fgemm(FGemmArgs
       kst[s] = p.b_sk * 1024;
     }
   }
-  u32x4_t pre[C::PASSES];
-
   f32x16_t acc[WI][WJ];
 #pragma unroll
   for (int i = 0; i < WI; ++i)
@@ -120,37 +119,67 @@ __global__ void __launch_bounds__(256, (WI * WJ <= 8 ? 2 : 1)) k_fgemm(FGemmArgs
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  // (loads are unconditional, from a clamped step: the staging registers must stay registers)
-  {
-    const int k0 = kbeg < kend ? kbeg : 0;
+  // Pipeline: the LDS holds a ring of three steps; two register sets carry the steps on their way. In iteration c the
+  // products read step c from the ring, set X (step c+1, asked for two iterations ago) is written to the ring, step
+  // c+3 is asked for into X, one barrier, and the sets swap roles. Loads are unconditional from a clamped step, so
+  // the staging registers stay registers.
+  const int nch = kbeg < kend ? (kend - kbeg) / C::KC : 0;
+  u32x4_t preX[C::PASSES], preY[C::PASSES];
+  auto kclamp = [&](int ch) { return kbeg + (ch < nch ? ch : (nch > 0 ? nch - 1 : 0)) * C::KC; };
+  constexpr int STAGE = C::NF * 64;   // 16-byte units per ring slot
+  if (nch > 0) {
+    {
+      const long k0 = kclamp(0), k1 = kclamp(1), k2 = kclamp(2);
 #pragma unroll
-    for (int s = 0; s < C::PASSES; ++s) pre[s] = *reinterpret_cast<const u32x4_t*>(src[s] + (long)k0 * kst[s]);
-  }
-  for (int kb = kbeg; kb < kend; kb += C::KC) {
-    __syncthreads();   // the previous step's fragments have been consumed
+      for (int s = 0; s < C::PASSES; ++s) preX[s] = *reinterpret_cast<const u32x4_t*>(src[s] + k0 * kst[s]);
 #pragma unroll
-    for (int s = 0; s < C::PASSES; ++s) lds[(4 * s + wave) * 64 + lane] = pre[s];
-    __syncthreads();
-    {  // the next step travels during the products (the last step loads itself again)
-      const int kn = kb + C::KC < kend ? kb + C::KC : kb;
+      for (int s = 0; s < C::PASSES; ++s) preY[s] = *reinterpret_cast<const u32x4_t*>(src[s] + k1 * kst[s]);
 #pragma unroll
-      for (int s = 0; s < C::PASSES; ++s) pre[s] = *reinterpret_cast<const u32x4_t*>(src[s] + (long)kn * kst[s]);
+      for (int s = 0; s < C::PASSES; ++s) lds[(4 * s + wave) * 64 + lane] = preX[s];
+#pragma unroll
+      for (int s = 0; s < C::PASSES; ++s) preX[s] = *reinterpret_cast<const u32x4_t*>(src[s] + k2 * kst[s]);
     }
+    __syncthreads();
+    // after the prologue: ring slot 0 = step 0, Y = step 1, X = step 2
+    int slot = 0;
+    for (int c = 0; c < nch; c += 2) {
 #pragma unroll
-    for (int kk = 0; kk < C::KC; ++kk) {
-      bf16x8_t a[WI], b[WJ];
+      for (int par = 0; par < 2; ++par) {
+        const int cc = c + par;
+        if (cc < nch) {   // uniform
+          const u32x4_t* cur = lds + slot * STAGE;
+          const int nslot = slot == 2 ? 0 : slot + 1;
 #pragma unroll
-      for (int i = 0; i < WI; ++i) {
-        a[i] = __builtin_bit_cast(bf16x8_t, lds[(kk * C::TI + wi * WI + i) * 64 + lane]);
+          for (int kk = 0; kk < C::KC; ++kk) {
+            bf16x8_t a[WI], b[WJ];
+#pragma unroll
+            for (int i = 0; i < WI; ++i) a[i] = __builtin_bit_cast(bf16x8_t, cur[(kk * C::TI + wi * WI + i) * 64 + lane]);
+#pragma unroll
+            for (int j = 0; j < WJ; ++j)
+              b[j] = __builtin_bit_cast(bf16x8_t, cur[(C::KC * C::TI + kk * C::TJ + wj * WJ + j) * 64 + lane]);
+#pragma unroll
+            for (int i = 0; i < WI; ++i)
+#pragma unroll
+              for (int j = 0; j < WJ; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+          }
+          // step cc+1 into the ring, step cc+3 on its way (even iterations use set Y, odd ones set X)
+          const long kn = kclamp(cc + 3);
+          if (par == 0) {
+#pragma unroll
+            for (int s = 0; s < C::PASSES; ++s) lds[nslot * STAGE + (4 * s + wave) * 64 + lane] = preY[s];
+#pragma unroll
+            for (int s = 0; s < C::PASSES; ++s) preY[s] = *reinterpret_cast<const u32x4_t*>(src[s] + kn * kst[s]);
+          } else {
+#pragma unroll
+            for (int s = 0; s < C::PASSES; ++s) lds[nslot * STAGE + (4 * s + wave) * 64 + lane] = preX[s];
+#pragma unroll
+            for (int s = 0; s < C::PASSES; ++s) preX[s] = *reinterpret_cast<const u32x4_t*>(src[s] + kn * kst[s]);
+          }
+          __syncthreads();
+          slot = nslot;
+        }
       }
-#pragma unroll
-      for (int j = 0; j < WJ; ++j) {
-        b[j] = __builtin_bit_cast(bf16x8_t, lds[(C::KC * C::TI + kk * C::TJ + wj * WJ + j) * 64 + lane]);
-      }
-#pragma unroll
-      for (int i = 0; i < WI; ++i)
-#pragma unroll
-        for (int j = 0; j < WJ; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
     }
   }
 
@@ -214,6 +243,12 @@ static int32_t launch_fgemm_t(hipStream_t st, const FGemmArgs& a) {
   const long nTi = a.nI / C::TI, nTj = a.nJ / C::TJ;
   const long gx = EPI == EPI_PART ? (long)a.nsplit * nTi * nTj : (nTi + 7) / 8 * 8 * nTj;
   HGNN_REQUIRE(gx <= 2147483647L && groups <= 65535, HGNN_ERR_OVERFLOW, "fragment GEMM: grid too large");
+  static bool lds_set = false;   // the ring may exceed the default dynamic LDS limit: raise it once per variant
+  if (!lds_set) {
+    HGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_fgemm<WI, WJ, EPI>),
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES));
+    lds_set = true;
+  }
   ProfScope ps(a.tag, st);
   k_fgemm<WI, WJ, EPI><<<dim3((unsigned)gx, 1, groups), 256, C::LDS_BYTES, st>>>(a);
   HGNN_LAUNCH_CHECK("k_fgemm");
@@ -438,11 +473,17 @@ __global__ void __launch_bounds__(256) k_reduce_wgrad(const float* __restrict__ 
 }
 
 // ---------------------------------------------------------------------------------------------
-// edge kernels on 8 x 8 micro-blocks: 8 rows of one row set (T order) x 8 consecutive columns per thread
+// element-wise edge kernels. A workgroup walks tiles of 32 edges (one row block) x 64 columns:
+//   compute mapping, thread (q, x) = (tid >> 6, tid & 63): the 8 edges of row set (row group 2 rb32 + (q >> 1), lane
+//     half q & 1) in column 64 slab + x. T fragments are loaded and stored in this mapping: a wavefront moves two
+//     contiguous half fragments with one 16-byte access per lane.
+//   R mapping (through an LDS copy of the tile), thread (q, x): contraction block 4 slab + q, lane x of the fragment
+//     (row x & 31, 8 columns from 8 (x >> 5)): a wavefront stores one whole 1 KiB fragment.
+// Every global store instruction therefore writes whole cache lines.
 // ---------------------------------------------------------------------------------------------
 struct EdgeElemArgs {
   int64_t E = 0;
-  long nrs = 0;            // row sets covered (padded rows / 8)
+  int nrb = 0;             // 32-row blocks covered (padded rows / 32)
   int H = 0, Hp = 0;
   const int32_t* dst = nullptr;
   const int32_t* col = nullptr;
@@ -462,7 +503,7 @@ struct EdgeElemArgs {
   char* gz2_T = nullptr;
   char* ga1_T = nullptr;                // g_a1 in, g_z1 out (in place)
   unsigned short* gz1_rm = nullptr;     // g_z1 again, bf16 row-major [rows, Hp]: what the source-sorted sum gathers
-  float* colpart = nullptr;             // [blocks][2][Hp] column-sum partials
+  float* colpart = nullptr;             // [gridDim.y][2][Hp] column-sum partials
 };
 
 __device__ __forceinline__ void unpack8(const uint4 w, float (&f)[8]) {
@@ -475,178 +516,147 @@ __device__ __forceinline__ uint4 pack8(const float (&f)[8]) {
   w.z = pack_bf16x2(f[4], f[5]); w.w = pack_bf16x2(f[6], f[7]);
   return w;
 }
-// stores of one micro-block v[u][k] (row slot u, column c0 + k)
-__device__ __forceinline__ void store_R(char* R, int nkb, int rb16, int g, int c0, const float (&v)[8][8]) {
-#pragma unroll
-  for (int u = 0; u < 8; ++u) {
-    const int r = tset_row(rb16, g, u);
-    const long frag = (long)(r >> 5) * nkb + (c0 >> 4);
-    *reinterpret_cast<uint4*>(R + (frag * 64 + ((c0 >> 3) & 1) * 32 + (r & 31)) * 16) = pack8(v[u]);
-  }
-}
-__device__ __forceinline__ void store_T(char* T, int ncb, int rb16, int g, int c0, const float (&v)[8][8]) {
-  const long frag = (long)rb16 * ncb + (c0 >> 5);
-#pragma unroll
-  for (int k = 0; k < 8; ++k) {
-    float col[8];
-#pragma unroll
-    for (int u = 0; u < 8; ++u) col[u] = v[u][k];
-    *reinterpret_cast<uint4*>(T + (frag * 64 + g * 32 + (c0 & 31) + k) * 16) = pack8(col);
-  }
-}
-__device__ __forceinline__ void load_T(const char* T, int ncb, int rb16, int g, int c0, float (&v)[8][8]) {
-  const long frag = (long)rb16 * ncb + (c0 >> 5);
-#pragma unroll
-  for (int k = 0; k < 8; ++k) {
-    float col[8];
-    unpack8(*reinterpret_cast<const uint4*>(T + (frag * 64 + g * 32 + (c0 & 31) + k) * 16), col);
-#pragma unroll
-    for (int u = 0; u < 8; ++u) v[u][k] = col[u];
-  }
-}
 
-// z1 of the micro-block from the gathered atom projections; rows past E give zeros
-__device__ __forceinline__ void gather_z1(const EdgeElemArgs& p, int rb16, int g, int c0, const float (&w1)[8],
-                                          float (&z)[8][8], bool (&ok)[8]) {
-#pragma unroll
-  for (int u = 0; u < 8; ++u) {
-    const long r = tset_row(rb16, g, u);
-    ok[u] = r < p.E;
-    const long rr = ok[u] ? r : 0;
-    const long di = ok[u] ? p.dst[rr] : 0, ci = ok[u] ? p.col[rr] : 0;
-    const float dd = ok[u] ? p.d2[rr] : 0.f;
-    float pf[8], qf[8];
-    unpack8(*reinterpret_cast<const uint4*>(p.PQ + di * 2 * p.Hp + c0), pf);
-    unpack8(*reinterpret_cast<const uint4*>(p.PQ + ci * 2 * p.Hp + p.Hp + c0), qf);
-#pragma unroll
-    for (int k = 0; k < 8; ++k) z[u][k] = pf[k] + qf[k] + dd * w1[k];
-  }
-}
+enum { EE_A1 = 0, EE_GZ2 = 1, EE_GZ1 = 2 };
+constexpr int EE_PITCH = 72;   // LDS tile row pitch in bf16 elements (64 + 8: 16-byte reads of a column of rows spread over the banks)
 
-__global__ void __launch_bounds__(256) k_edge_a1(EdgeElemArgs p) {
-  const int CG = p.Hp >> 3;
-  const long idx = (long)blockIdx.x * 256 + threadIdx.x;
-  const int cg = (int)(idx % CG);
-  const long rs = idx / CG;
-  if (rs >= p.nrs) return;
-  const int rb16 = (int)(rs >> 1), g = (int)(rs & 1), c0 = cg * 8;
-  float w1[8];
+// EE_A1:  a1 = silu(P[dst] + Q[col] + d2 w1d)                                   -> R and T
+// EE_GZ2: g_z2 = (alpha g_M[dst] + c_e wx) silu'(z2)                            -> R and T; sums: g_b2 = sum g_z2, g_wx = sum c_e silu(z2)
+// EE_GZ1: g_z1 = g_a1 silu'(z1), z1 recomputed from the gathers                 -> T in place and row-major; sums: g_b1 = sum g_z1, g_w1d = sum d2 g_z1
+constexpr int EE_U = 1;   // tiles in flight per workgroup: all their loads are issued before the first is used
+template <int MODE>
+__global__ void __launch_bounds__(256) k_edge_elem(EdgeElemArgs p) {
+  __shared__ __align__(16) unsigned short tile[EE_U][32 * EE_PITCH];
+  __shared__ float csum[4][2][64];
+  const int tid = threadIdx.x, x = tid & 63;
+  const int q = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int slab = blockIdx.x;
+  const int c = slab * 64 + x;
+  const int ncb = p.Hp >> 5, nkb = p.Hp >> 4;
+  const int hh = q >> 1, g = q & 1;
+  const float wcol = c < p.H ? (MODE == EE_GZ2 ? p.wx[c] : p.w1d[c]) : 0.f;   // wx or w1d of this thread's column
+  const long lastrow = p.E > 0 ? p.E - 1 : 0;
+  char* Tdst = MODE == EE_A1 ? p.a1_T : (MODE == EE_GZ2 ? p.gz2_T : p.ga1_T);
+  float s0 = 0.f, s1 = 0.f;
+  for (int rb0 = blockIdx.y; rb0 < p.nrb; rb0 += EE_U * gridDim.y) {
+    // ---- loads of up to EE_U tiles (row blocks rb0 + t gridDim.y; blocks past the end are clamped and not stored)
+    u32x4_t tin[EE_U];
+    unsigned short ga[EE_U][8], gb[EE_U][8];
+    float sc[EE_U][8], sd[EE_U][8];
 #pragma unroll
-  for (int k = 0; k < 8; ++k) w1[k] = c0 + k < p.H ? p.w1d[c0 + k] : 0.f;
-  float z[8][8];
-  bool ok[8];
-  gather_z1(p, rb16, g, c0, w1, z, ok);
+    for (int t = 0; t < EE_U; ++t) {
+      const int rbt = rb0 + t * (int)gridDim.y;
+      const int rb = rbt < p.nrb ? rbt : p.nrb - 1;
+      const int rb16 = 2 * rb + hh;
+      const long tfrag = ((long)rb16 * ncb + (c >> 5)) * 1024 + (g * 32 + (c & 31)) * 16;
+      if (MODE == EE_GZ2) tin[t] = *reinterpret_cast<const u32x4_t*>(p.z2_T + tfrag);
+      if (MODE == EE_GZ1) tin[t] = *reinterpret_cast<const u32x4_t*>(p.ga1_T + tfrag);
 #pragma unroll
-  for (int u = 0; u < 8; ++u)
-#pragma unroll
-    for (int k = 0; k < 8; ++k) z[u][k] = ok[u] ? silu_f(z[u][k]) : 0.f;
-  store_R(p.a1_R, p.Hp / 16, rb16, g, c0, z);
-  store_T(p.a1_T, p.Hp / 32, rb16, g, c0, z);
-}
-
-// The two reverse kernels run blocks of (Hp / 8) x RS threads (column group x row set) that walk the row sets with a
-// grid stride and leave per-block column sums: colpart[block][0 / 1][Hp].
-__device__ __forceinline__ void write_colpart(float* sh, float* colpart, int Hp, const float (&s0)[8], const float (&s1)[8]) {
-  // sh: [blockDim.y][2][Hp]
-  const int c0 = threadIdx.x * 8;
-  float* mine = sh + (long)threadIdx.y * 2 * Hp;
-#pragma unroll
-  for (int k = 0; k < 8; ++k) {
-    mine[c0 + k] = s0[k];
-    mine[Hp + c0 + k] = s1[k];
-  }
-  __syncthreads();
-  if (threadIdx.y == 0) {
-    float* out = colpart + (long)blockIdx.x * 2 * Hp;
-#pragma unroll
-    for (int k = 0; k < 8; ++k) {
-      float a = 0.f, b = 0.f;
-      for (int y = 0; y < (int)blockDim.y; ++y) {   // row sets of the block in order
-        a += sh[(long)y * 2 * Hp + c0 + k];
-        b += sh[(long)y * 2 * Hp + Hp + c0 + k];
+      for (int u = 0; u < 8; ++u) {
+        const long r = tset_row(rb16, g, u);     // the same for all lanes of the wavefront
+        const long rr = r < p.E ? r : lastrow;
+        const long di = p.dst[rr];
+        if (MODE == EE_GZ2) {
+          sc[t][u] = p.cvec[rr];
+          ga[t][u] = p.gM[di * p.ldgM + c];
+        } else {
+          const long ci = p.col[rr];
+          sd[t][u] = p.d2[rr];
+          ga[t][u] = p.PQ[di * 2 * p.Hp + c];
+          gb[t][u] = p.PQ[ci * 2 * p.Hp + p.Hp + c];
+        }
       }
-      out[c0 + k] = a;
-      out[Hp + c0 + k] = b;
+    }
+    // ---- arithmetic and the T stores
+    u32x4_t packed[EE_U];
+#pragma unroll
+    for (int t = 0; t < EE_U; ++t) {
+      const int rbt = rb0 + t * (int)gridDim.y;
+      const bool live = rbt < p.nrb;
+      const int rb16 = 2 * rbt + hh;
+      float in[8], out[8];
+      if (MODE != EE_A1) {
+        const unsigned w4[4] = {tin[t][0], tin[t][1], tin[t][2], tin[t][3]};
+#pragma unroll
+        for (int u = 0; u < 8; ++u) in[u] = (u & 1) ? bf_hi(w4[u >> 1]) : bf_lo(w4[u >> 1]);
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const bool ok = live && tset_row(rb16, g, u) < p.E;
+        if (MODE == EE_GZ2) {
+          float y, dy;
+          silu_both(in[u], y, dy);
+          const float gz = ok ? fmaf(sc[t][u], wcol, p.alpha * bf_lo(ga[t][u])) * dy : 0.f;
+          s0 += gz;
+          s1 += ok ? sc[t][u] * y : 0.f;
+          out[u] = gz;
+        } else {
+          const float z = bf_lo(ga[t][u]) + bf_lo(gb[t][u]) + sd[t][u] * wcol;
+          if (MODE == EE_A1) {
+            out[u] = ok ? silu_f(z) : 0.f;
+          } else {
+            const float gz = ok ? in[u] * dsilu_f(z) : 0.f;
+            s0 += gz;
+            s1 += ok ? sd[t][u] * gz : 0.f;
+            out[u] = gz;
+          }
+        }
+      }
+      packed[t][0] = pack_bf16x2(out[0], out[1]);
+      packed[t][1] = pack_bf16x2(out[2], out[3]);
+      packed[t][2] = pack_bf16x2(out[4], out[5]);
+      packed[t][3] = pack_bf16x2(out[6], out[7]);
+      if (live) {
+        const long tfrag = ((long)rb16 * ncb + (c >> 5)) * 1024 + (g * 32 + (c & 31)) * 16;
+        *reinterpret_cast<u32x4_t*>(Tdst + tfrag) = packed[t];
+      }
+    }
+    // ---- the tiles in row-major order for the second mapping (rows of this row set: 16 hh + 8 (u >> 2) + 4 g + (u & 3))
+    __syncthreads();   // the previous tiles have been read
+#pragma unroll
+    for (int t = 0; t < EE_U; ++t) {
+      const unsigned w4[4] = {packed[t][0], packed[t][1], packed[t][2], packed[t][3]};
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int lr = 16 * hh + 8 * (u >> 2) + 4 * g + (u & 3);
+        tile[t][lr * EE_PITCH + x] = (unsigned short)((u & 1) ? (w4[u >> 1] >> 16) : (w4[u >> 1] & 0xffffu));
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int t = 0; t < EE_U; ++t) {
+      const int rbt = rb0 + t * (int)gridDim.y;
+      if (rbt < p.nrb) {
+        if (MODE == EE_GZ1) {
+          // row-major copy: thread -> row tid >> 3, 16-byte piece tid & 7 of the tile's 128-byte row segment
+          const int lr = tid >> 3, pc = tid & 7;
+          const u32x4_t w = *reinterpret_cast<const u32x4_t*>(&tile[t][lr * EE_PITCH + pc * 8]);
+          *reinterpret_cast<u32x4_t*>(p.gz1_rm + ((long)rbt * 32 + lr) * p.Hp + slab * 64 + pc * 8) = w;
+        } else {
+          const int lr = x & 31, g2 = x >> 5;
+          const u32x4_t w = *reinterpret_cast<const u32x4_t*>(&tile[t][lr * EE_PITCH + q * 16 + g2 * 8]);
+          char* Rdst = MODE == EE_A1 ? p.a1_R : p.gz2_R;
+          *reinterpret_cast<u32x4_t*>(Rdst + (((long)rbt * nkb + 4 * slab + q) * 64 + x) * 16) = w;
+        }
+      }
+    }
+  }
+  if (MODE != EE_A1) {
+    // column sums of the workgroup: the four row sets are added in order
+    csum[q][0][x] = s0;
+    csum[q][1][x] = s1;
+    __syncthreads();
+    if (q == 0) {
+      float* o = p.colpart + (long)blockIdx.y * 2 * p.Hp + c;
+      o[0] = ((csum[0][0][x] + csum[1][0][x]) + csum[2][0][x]) + csum[3][0][x];
+      o[p.Hp] = ((csum[0][1][x] + csum[1][1][x]) + csum[2][1][x]) + csum[3][1][x];
     }
   }
 }
 
-// g_z2 = (alpha g_M[dst] + c_e wx) silu'(z2); column sums: [0] g_b2 = sum g_z2, [1] g_wx = sum c_e silu(z2)
-__global__ void __launch_bounds__(256) k_edge_gz2(EdgeElemArgs p) {
-  extern __shared__ float sh[];
-  const int c0 = threadIdx.x * 8;
-  float wxv[8];
-#pragma unroll
-  for (int k = 0; k < 8; ++k) wxv[k] = c0 + k < p.H ? p.wx[c0 + k] : 0.f;
-  float s0[8] = {}, s1[8] = {};
-  for (long rs = (long)blockIdx.x * blockDim.y + threadIdx.y; rs < p.nrs; rs += (long)gridDim.x * blockDim.y) {
-    const int rb16 = (int)(rs >> 1), g = (int)(rs & 1);
-    float z[8][8];
-    load_T(p.z2_T, p.Hp / 32, rb16, g, c0, z);
-#pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      const long r = tset_row(rb16, g, u);
-      const bool ok = r < p.E;
-      const long di = ok ? p.dst[r] : 0;
-      const float cc = ok ? p.cvec[r] : 0.f;
-      float gm[8];
-      unpack8(*reinterpret_cast<const uint4*>(p.gM + di * p.ldgM + c0), gm);
-#pragma unroll
-      for (int k = 0; k < 8; ++k) {
-        float y, dy;
-        silu_both(z[u][k], y, dy);
-        const float gz = ok ? fmaf(cc, wxv[k], p.alpha * gm[k]) * dy : 0.f;
-        s0[k] += gz;
-        s1[k] += ok ? cc * y : 0.f;
-        z[u][k] = gz;
-      }
-    }
-    store_R(p.gz2_R, p.Hp / 16, rb16, g, c0, z);
-    store_T(p.gz2_T, p.Hp / 32, rb16, g, c0, z);
-  }
-  write_colpart(sh, p.colpart, p.Hp, s0, s1);
-}
-
-// g_z1 = g_a1 silu'(z1) (in place, T); column sums: [0] g_b1 = sum g_z1, [1] g_w1d = sum d2_e g_z1
-__global__ void __launch_bounds__(256) k_edge_gz1(EdgeElemArgs p) {
-  extern __shared__ float sh[];
-  const int c0 = threadIdx.x * 8;
-  float w1[8];
-#pragma unroll
-  for (int k = 0; k < 8; ++k) w1[k] = c0 + k < p.H ? p.w1d[c0 + k] : 0.f;
-  float s0[8] = {}, s1[8] = {};
-  for (long rs = (long)blockIdx.x * blockDim.y + threadIdx.y; rs < p.nrs; rs += (long)gridDim.x * blockDim.y) {
-    const int rb16 = (int)(rs >> 1), g = (int)(rs & 1);
-    float z[8][8], ga[8][8];
-    bool ok[8];
-    gather_z1(p, rb16, g, c0, w1, z, ok);
-    load_T(p.ga1_T, p.Hp / 32, rb16, g, c0, ga);
-#pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      const long r = tset_row(rb16, g, u);
-      const float dd = ok[u] ? p.d2[r] : 0.f;
-#pragma unroll
-      for (int k = 0; k < 8; ++k) {
-        const float gz = ok[u] ? ga[u][k] * dsilu_f(z[u][k]) : 0.f;
-        s0[k] += gz;
-        s1[k] += dd * gz;
-        ga[u][k] = gz;
-      }
-    }
-    store_T(p.ga1_T, p.Hp / 32, rb16, g, c0, ga);
-#pragma unroll
-    for (int u = 0; u < 8; ++u)
-      *reinterpret_cast<uint4*>(p.gz1_rm + (long)tset_row(rb16, g, u) * p.Hp + c0) = pack8(ga[u]);
-  }
-  write_colpart(sh, p.colpart, p.Hp, s0, s1);
-}
-
-constexpr int ELEM_MAX_BLOCKS = 1024;   // per-block column-sum partials kept by the reverse edge kernels
-static dim3 elem_block(int Hp) { return dim3(Hp / 8, 256 / (Hp / 8) > 0 ? 256 / (Hp / 8) : 1); }
-static int elem_grid(long nrs, int Hp) {
-  const long per = elem_block(Hp).y;
-  const long need = (nrs + per - 1) / per;
-  return (int)(need < ELEM_MAX_BLOCKS ? (need < 1 ? 1 : need) : ELEM_MAX_BLOCKS);
+constexpr int ELEM_MAX_BLOCKS = 256;   // row-block phases (= column-sum partials) of the element-wise edge kernels
+static dim3 elem_grid(int nrb, int Hp) {
+  return dim3(Hp / 64, nrb < 1 ? 1 : (nrb < ELEM_MAX_BLOCKS ? nrb : ELEM_MAX_BLOCKS));
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -993,7 +1003,12 @@ int32_t launch_fwgrad(hipStream_t st, const FWgradArgs& a) {
   HGNN_LAUNCH_CHECK("k_reduce_wgrad");
   return HGNN_OK;
 }
-int32_t launch_fgemm_rows(hipStream_t st, const FGemmArgs& a) { return launch_fgemm_t<4, 2, EPI_ROW>(st, a); }
+int32_t launch_fgemm_rows(hipStream_t st, const FGemmArgs& a) {
+  // few rows (atoms, graphs): 128 x 128 tiles give the launch enough workgroups to cover the chip
+  const long big_tiles = (long)((a.nI + 7) / 8) * (a.nJ / 4) * (a.grp_ptr ? a.S : 1);
+  if (big_tiles < 4L * num_cus()) return launch_fgemm_t<2, 2, EPI_ROW>(st, a);
+  return launch_fgemm_t<4, 2, EPI_ROW>(st, a);
+}
 int32_t launch_fgemm_rows_T(hipStream_t st, const FGemmArgs& a) { return launch_fgemm_t<4, 2, EPI_T>(st, a); }
 
 // layer-level shorthand: square Hp blocks, no groups
@@ -1058,18 +1073,17 @@ int32_t wide_layer_fwd(hipStream_t st, const WideLayerArgs& a) {
     g.b_sj = d.nkb;
     g.M = d.N; g.Cb = s.PQ; g.ldcb = 2 * Hp;
     g.bias = W + o.b1; g.nbias = H;
-    HGNN_TRY((launch_fgemm_t<4, 2, EPI_ROW>(st, g)));
+    HGNN_TRY(launch_fgemm_rows(st, g));
   }
   EdgeElemArgs e;
-  e.E = d.E; e.nrs = d.Ep / 8; e.H = H; e.Hp = Hp;
+  e.E = d.E; e.nrb = (int)(d.Ep / 32); e.H = H; e.Hp = Hp;
   e.dst = a.dst; e.col = a.col; e.d2 = a.d2; e.PQ = s.PQ; e.w1d = W + o.W1 + 2 * HH;
   e.a1_R = s.a1_R; e.a1_T = s.a1_T;
   if (d.Ep > 0) {
     {
       ProfScope ps(PT_EDGE_ELEM, st);
-      const long n = e.nrs * (Hp / 8);
-      k_edge_a1<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(e);
-      HGNN_LAUNCH_CHECK("k_edge_a1");
+      k_edge_elem<EE_A1><<<elem_grid(e.nrb, Hp), 256, 0, st>>>(e);
+      HGNN_LAUNCH_CHECK("k_edge_elem (a1)");
     }
     // z2 = a1 W2 + b2 (T fragments)
     FGemmArgs g = nn_args(s.a1_R, d.nkb, (int)(d.Ep / 32), w.packed + 2 * PP, d.ncb, PT_FRAG_GEMM_EDGE);
@@ -1089,7 +1103,7 @@ int32_t wide_layer_fwd(hipStream_t st, const WideLayerArgs& a) {
     FGemmArgs g = nn_args(w.hM_R, 2 * d.nkb, d.Np / 32, w.packed + 3 * PP, d.ncb, PT_GEMM_NODE);
     g.M = d.N; g.Cf = s.z3; g.ldc = Hp; g.ncol_f = Hp;
     g.bias = W + o.b3; g.nbias = H;
-    HGNN_TRY((launch_fgemm_t<4, 2, EPI_ROW>(st, g)));
+    HGNN_TRY(launch_fgemm_rows(st, g));
   }
   {  // a3 = silu(z3)
     ToFragArgs t;
@@ -1102,7 +1116,7 @@ int32_t wide_layer_fwd(hipStream_t st, const WideLayerArgs& a) {
     g.M = d.N; g.Cf = a.h_out; g.ldc = H; g.ncol_f = H;
     g.r1 = a.h_in; g.ld1 = H;
     g.bias = W + o.b4; g.nbias = H;
-    HGNN_TRY((launch_fgemm_t<4, 2, EPI_ROW>(st, g)));
+    HGNN_TRY(launch_fgemm_rows(st, g));
   }
   return HGNN_OK;
 }
@@ -1164,7 +1178,7 @@ int32_t wide_layer_bwd(hipStream_t st, const WideLayerArgs& a) {
   {  // g_a3 = g_h' W4^T
     FGemmArgs g = nn_args(w.x_R, d.nkb, d.Np / 32, w.packed, d.ncb, PT_GEMM_NODE);
     g.M = d.N; g.Cf = w.nodeA; g.ldc = Hp; g.ncol_f = Hp;
-    HGNN_TRY((launch_fgemm_t<4, 2, EPI_ROW>(st, g)));
+    HGNN_TRY(launch_fgemm_rows(st, g));
   }
   {  // g_z3 = g_a3 silu'(z3) as R and T; g_b3 = its column sums
     ToFragArgs t;
@@ -1181,23 +1195,22 @@ int32_t wide_layer_bwd(hipStream_t st, const WideLayerArgs& a) {
     FGemmArgs g = nn_args(w.x_R, d.nkb, d.Np / 32, w.packed + PP, 2 * d.ncb, PT_GEMM_NODE);
     g.M = d.N; g.Cf = w.nodeA; g.ldc = 2 * Hp; g.ncol_f = 2 * Hp;
     g.Cb = w.gM_b; g.ldcb = 2 * Hp;
-    HGNN_TRY((launch_fgemm_t<4, 2, EPI_ROW>(st, g)));
+    HGNN_TRY(launch_fgemm_rows(st, g));
   }
   // edge part
   EdgeElemArgs e;
-  e.E = d.E; e.nrs = d.Ep / 8; e.H = H; e.Hp = Hp;
+  e.E = d.E; e.nrb = (int)(d.Ep / 32); e.H = H; e.Hp = Hp;
   e.dst = a.dst; e.col = a.col; e.d2 = a.d2; e.PQ = s.PQ; e.w1d = W + o.W1 + 2 * HH;
   e.z2_T = s.z2_T; e.gM = w.gM_b + Hp; e.ldgM = 2 * Hp; e.cvec = w.cvec; e.wx = W + o.wx; e.alpha = a.alpha;
   e.gz2_R = w.gz2_R; e.gz2_T = w.gz2_T; e.ga1_T = w.ga1_T; e.colpart = w.colpart;
   e.gz1_rm = reinterpret_cast<unsigned short*>(w.gz2_R);   // free again once g_a1 has been formed
-  const dim3 eb = elem_block(Hp);
-  const int eg = elem_grid(e.nrs, Hp);
-  const size_t esh = (size_t)eb.y * 2 * Hp * sizeof(float);
+  const dim3 egrid = elem_grid(e.nrb, Hp);
+  const int eg = (int)egrid.y;   // column-sum partials
   HGNN_TRY(launch_edge_cvec(st, d.E, a.dst, a.rvec, a.g_v_out, a.alpha, w.cvec));
   {
     ProfScope ps(PT_EDGE_ELEM, st);
-    k_edge_gz2<<<eg, eb, esh, st>>>(e);
-    HGNN_LAUNCH_CHECK("k_edge_gz2");
+    k_edge_elem<EE_GZ2><<<egrid, 256, 0, st>>>(e);
+    HGNN_LAUNCH_CHECK("k_edge_elem (g_z2)");
   }
   {
     ProfScope ps(PT_COLSUM, st);
@@ -1214,8 +1227,8 @@ int32_t wide_layer_bwd(hipStream_t st, const WideLayerArgs& a) {
   }
   {
     ProfScope ps(PT_EDGE_ELEM, st);
-    k_edge_gz1<<<eg, eb, esh, st>>>(e);
-    HGNN_LAUNCH_CHECK("k_edge_gz1");
+    k_edge_elem<EE_GZ1><<<egrid, 256, 0, st>>>(e);
+    HGNN_LAUNCH_CHECK("k_edge_elem (g_z1)");
   }
   {
     ProfScope ps(PT_COLSUM, st);
@@ -1245,7 +1258,7 @@ int32_t wide_layer_bwd(hipStream_t st, const WideLayerArgs& a) {
     g.M = d.N; g.Cf = a.g_h_in; g.ldc = H; g.ncol_f = H;
     g.r1 = a.g_h_out; g.ld1 = H;
     g.r2 = w.nodeA; g.ld2 = 2 * Hp;
-    HGNN_TRY((launch_fgemm_t<4, 2, EPI_ROW>(st, g)));
+    HGNN_TRY(launch_fgemm_rows(st, g));
   }
   if (a.g_v_in != a.g_v_out) HGNN_TRY(launch_copy_f32(st, a.g_v_out, a.g_v_in, (int64_t)d.N * 3));
   return HGNN_OK;
