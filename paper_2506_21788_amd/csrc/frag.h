@@ -50,7 +50,7 @@ struct FGemmArgs {
   long ldp = 0, split_stride = 0;
   int tag = PT_GEMM_NODE;
 };
-int32_t launch_fgemm_rows(hipStream_t st, const FGemmArgs& a);     // EPI_ROW, 256 x 128 tiles
+int32_t launch_fgemm_rows(hipStream_t st, const FGemmArgs& a);     // EPI_ROW, 256 x 128 tiles (128 x 128 for few rows)
 int32_t launch_fgemm_rows_T(hipStream_t st, const FGemmArgs& a);   // EPI_T, 256 x 128 tiles
 
 // dest[group * dest_grp_stride + pa * strideA + pb * strideB + r1 * HB + r2] = (A^T B)[pa * HpA + r1][pb * HpB + r2]
@@ -75,16 +75,17 @@ int32_t launch_fwgrad(hipStream_t st, const FWgradArgs& a);
 struct PackPart {
   long src_off;        // B[k][n] = src[src_off + k * sk + n * sn] for k < K, n < Nn, else 0
   int sk, sn;
-  int kb0, nb0;        // where the part's (Kp/16 x Np/32) fragments sit in the destination
+  long dst_off;        // element offset of the destination matrix this part belongs to
+  int nkb_total;       // fragments per column block of that destination
+  int kb0, nb0;        // where the part's (Kp/16 x Np/32) fragments sit in it
 };
 struct PackFragArgs {
   const float* src = nullptr;
   unsigned short* dst = nullptr;
-  int nkb_total = 0;   // fragments per column block of the destination
   int K = 0, Nn = 0;   // valid extent of every part
   int Kp = 0, Np = 0;  // padded extent of every part
   int nparts = 0;
-  PackPart part[4];
+  PackPart part[8];
   int groups = 1;
   long src_grp_stride = 0, dst_grp_stride = 0;   // elements
 };

@@ -199,11 +199,11 @@ static int32_t pack_layer(hipStream_t st, const DeepDims& d, const DeepOff& o, c
   pk.src = Whead; pk.dst = dst; pk.nparts = 1;
   pk.groups = d.S; pk.src_grp_stride = o.per; pk.dst_grp_stride = (long)Kp * d.Hhp;
   if (!transposed) {
-    pk.K = K; pk.Nn = d.Hh; pk.Kp = Kp; pk.Np = d.Hhp; pk.nkb_total = Kp / 16;
-    pk.part[0] = {o.W[hd][l], d.Hh, 1, 0, 0};
+    pk.K = K; pk.Nn = d.Hh; pk.Kp = Kp; pk.Np = d.Hhp;
+    pk.part[0] = {o.W[hd][l], d.Hh, 1, 0, Kp / 16, 0, 0};
   } else {
-    pk.K = d.Hh; pk.Nn = K; pk.Kp = d.Hhp; pk.Np = Kp; pk.nkb_total = d.Hhp / 16;
-    pk.part[0] = {o.W[hd][l], 1, d.Hh, 0, 0};
+    pk.K = d.Hh; pk.Nn = K; pk.Kp = d.Hhp; pk.Np = Kp;
+    pk.part[0] = {o.W[hd][l], 1, d.Hh, 0, d.Hhp / 16, 0, 0};
   }
   return launch_pack_frag(st, pk);
 }

@@ -6,10 +6,9 @@
 //   k_to_frag      row-major fp32 atom tensor -> R and / or T fragments (optionally silu(x) or x * silu'(z))
 //   k_edge_elem    the three element-wise edge kernels on 32 x 64 tiles: a1 = silu(P[dst] + Q[col] + d2 w1d) -> R, T;
 //                  g_z2 = (alpha g_M[dst] + c_e wx) silu'(z2) -> R, T (+ column sums for g_b2, g_wx);
-//                  g_z1 = g_a1 silu'(z1) -> T in place and row-major (+ column sums for g_b1, g_w1d)
+//                  g_z1 = g_a1 silu'(z1) -> row-major (+ column sums for g_b1, g_w1d)
 //   k_seg_fwd_w    M_i = alpha sum silu(z2), v'_i = v_i + alpha sum (wx . m_e) rvec_e   (one wavefront per atom)
-//   k_segsum_w     per-atom sums of g_z1 over the destination-sorted rows (T fragments)
-//   k_segsum_rows  per-atom sums of g_z1 over the source-sorted edge list (row gathers of the row-major copy)
+//   k_segsum_rows  per-atom sums of g_z1 over the destination-sorted rows and over the source-sorted edge list
 // The layer follows the same algebra as the narrow path: the first edge layer is split by linearity into per-atom
 // products P = h W1a + b1, Q = h W1b that the edges gather.
 #include "wide.h"
@@ -273,7 +272,7 @@ __global__ void __launch_bounds__(256) k_pack_frag(PackFragArgs a) {
   const int k = kb * 16 + (lane >> 5) * 8 + u, n = nb * 32 + (lane & 31);
   float v = 0.f;
   if (k < a.K && n < a.Nn) v = a.src[blockIdx.z * a.src_grp_stride + pt.src_off + (long)k * pt.sk + (long)n * pt.sn];
-  a.dst[blockIdx.z * a.dst_grp_stride + (((long)(pt.nb0 + nb) * a.nkb_total + pt.kb0 + kb) * 64 + lane) * 8 + u] =
+  a.dst[blockIdx.z * a.dst_grp_stride + pt.dst_off + (((long)(pt.nb0 + nb) * pt.nkb_total + pt.kb0 + kb) * 64 + lane) * 8 + u] =
       (unsigned short)f2bf_bits(v);
 }
 
@@ -505,8 +504,8 @@ struct EdgeElemArgs {
   float alpha = 1.f;
   char* gz2_R = nullptr;
   char* gz2_T = nullptr;
-  char* ga1_T = nullptr;                // g_a1 in, g_z1 out (in place)
-  unsigned short* gz1_rm = nullptr;     // g_z1 again, bf16 row-major [rows, Hp]: what the source-sorted sum gathers
+  const char* ga1_T = nullptr;          // g_a1
+  unsigned short* gz1_rm = nullptr;     // g_z1, bf16 row-major [rows, Hp]: what the two per-atom sums read
   float* colpart = nullptr;             // [gridDim.y][2][Hp] column-sum partials
 };
 
@@ -526,7 +525,7 @@ constexpr int EE_PITCH = 72;   // LDS tile row pitch in bf16 elements (64 + 8: 1
 
 // EE_A1:  a1 = silu(P[dst] + Q[col] + d2 w1d)                                   -> R and T
 // EE_GZ2: g_z2 = (alpha g_M[dst] + c_e wx) silu'(z2)                            -> R and T; sums: g_b2 = sum g_z2, g_wx = sum c_e silu(z2)
-// EE_GZ1: g_z1 = g_a1 silu'(z1), z1 recomputed from the gathers                 -> T in place and row-major; sums: g_b1 = sum g_z1, g_w1d = sum d2 g_z1
+// EE_GZ1: g_z1 = g_a1 silu'(z1), z1 recomputed from the gathers                 -> row-major; sums: g_b1 = sum g_z1, g_w1d = sum d2 g_z1
 constexpr int EE_U = 1;   // tiles in flight per workgroup: all their loads are issued before the first is used
 template <int MODE>
 __global__ void __launch_bounds__(256) k_edge_elem(EdgeElemArgs p) {
@@ -540,7 +539,7 @@ __global__ void __launch_bounds__(256) k_edge_elem(EdgeElemArgs p) {
   const int hh = q >> 1, g = q & 1;
   const float wcol = c < p.H ? (MODE == EE_GZ2 ? p.wx[c] : p.w1d[c]) : 0.f;   // wx or w1d of this thread's column
   const long lastrow = p.E > 0 ? p.E - 1 : 0;
-  char* Tdst = MODE == EE_A1 ? p.a1_T : (MODE == EE_GZ2 ? p.gz2_T : p.ga1_T);
+  char* Tdst = MODE == EE_A1 ? p.a1_T : p.gz2_T;
   float s0 = 0.f, s1 = 0.f;
   for (int rb0 = blockIdx.y; rb0 < p.nrb; rb0 += EE_U * gridDim.y) {
     // ---- loads of up to EE_U tiles (row blocks rb0 + t gridDim.y; blocks past the end are clamped and not stored)
@@ -610,7 +609,7 @@ __global__ void __launch_bounds__(256) k_edge_elem(EdgeElemArgs p) {
       packed[t][1] = pack_bf16x2(out[2], out[3]);
       packed[t][2] = pack_bf16x2(out[4], out[5]);
       packed[t][3] = pack_bf16x2(out[6], out[7]);
-      if (live) {
+      if (live && MODE != EE_GZ1) {   // g_z1 is only read row by row: it goes out row-major below
         const long tfrag = ((long)rb16 * ncb + (c >> 5)) * 1024 + (g * 32 + (c & 31)) * 16;
         *reinterpret_cast<u32x4_t*>(Tdst + tfrag) = packed[t];
       }
@@ -726,55 +725,8 @@ __global__ void __launch_bounds__(256) k_seg_fwd_w(int N, const int32_t* __restr
   }
 }
 
-// out[i][32 cb + x] = sum over the edges of atom i's list of X[e][32 cb + x]  (X as T fragments).
-// perm == null: the list is the contiguous row range ptr[i] .. ptr[i+1] (whole fragments are read and masked);
-// else the list is perm[ptr[i] .. ptr[i+1]) and the two lane halves take alternate entries, one element at a time.
-template <int NCB>
-__global__ void __launch_bounds__(256) k_segsum_w(int N, const int32_t* __restrict__ ptr, const int32_t* __restrict__ perm,
-                                                  const char* __restrict__ X_T, float* __restrict__ out, long ldo) {
-  const int lane = threadIdx.x & 63, g = lane >> 5, x = lane & 31;
-  const int i = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (i >= N) return;
-  const int e0 = ptr[i], e1 = ptr[i + 1];
-  float acc[NCB];
-#pragma unroll
-  for (int cb = 0; cb < NCB; ++cb) acc[cb] = 0.f;
-  if (perm == nullptr) {
-    for (int rb16 = e0 >> 4; rb16 * 16 < e1; ++rb16) {
-      bool ok[8];
-#pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        const int r = tset_row(rb16, g, u);
-        ok[u] = r >= e0 && r < e1;
-      }
-#pragma unroll
-      for (int cb = 0; cb < NCB; ++cb) {
-        float zz[8];
-        unpack8(*reinterpret_cast<const uint4*>(X_T + (((long)rb16 * NCB + cb) * 64 + lane) * 16), zz);
-#pragma unroll
-        for (int u = 0; u < 8; ++u) acc[cb] += ok[u] ? zz[u] : 0.f;
-      }
-    }
-  } else {
-    for (int k = e0 + g; k < e1; k += 2) {
-      const int e = perm[k];
-      const int r = e & 15;
-      const int ge = (r >> 2) & 1, ue = ((r >> 3) << 2) | (r & 3);
-      const unsigned short* base =
-          reinterpret_cast<const unsigned short*>(X_T + ((long)(e >> 4) * NCB * 64 + ge * 32 + x) * 16) + ue;
-#pragma unroll
-      for (int cb = 0; cb < NCB; ++cb) acc[cb] += bf_lo(base[(long)cb * 512]);
-    }
-  }
-#pragma unroll
-  for (int cb = 0; cb < NCB; ++cb) {
-    const float t = acc[cb] + __shfl_xor(acc[cb], 32);
-    if (g == 0) out[(long)i * ldo + cb * 32 + x] = t;
-  }
-}
-
-// out[i][c] = sum over k in ptr[i] .. ptr[i+1] of X[perm[k]][c], X bf16 row-major with pitch Hp (one wavefront per
-// atom, 16-byte pieces of a row per lane, two rows in flight)
+// out[i][c] = sum over k in ptr[i] .. ptr[i+1] of X[perm[k]][c] (perm == null: X[k][c]), X bf16 row-major with pitch
+// Hp (one wavefront per atom, 16-byte pieces of a row per lane, two rows in flight)
 __global__ void __launch_bounds__(256) k_segsum_rows(int N, int Hp, const int32_t* __restrict__ ptr,
                                                      const int32_t* __restrict__ perm, const unsigned short* __restrict__ X,
                                                      float* __restrict__ out, long ldo) {
@@ -788,8 +740,8 @@ __global__ void __launch_bounds__(256) k_segsum_rows(int N, int Hp, const int32_
   const uint4 zero = make_uint4(0u, 0u, 0u, 0u);
   int k = e0;
   for (; k + 2 <= e1; k += 2) {
-    const unsigned short* r0 = X + (long)perm[k] * Hp;
-    const unsigned short* r1 = X + (long)perm[k + 1] * Hp;
+    const unsigned short* r0 = X + (long)(perm ? perm[k] : k) * Hp;
+    const unsigned short* r1 = X + (long)(perm ? perm[k + 1] : k + 1) * Hp;
     const uint4 w00 = *reinterpret_cast<const uint4*>(r0 + lane * 8);
     const uint4 w10 = *reinterpret_cast<const uint4*>(r1 + lane * 8);
     const uint4 w01 = two ? *reinterpret_cast<const uint4*>(r0 + (lane + 64) * 8) : zero;
@@ -809,7 +761,7 @@ __global__ void __launch_bounds__(256) k_segsum_rows(int N, int Hp, const int32_
     for (int u = 0; u < 8; ++u) a1[u] += f[u];
   }
   if (k < e1) {
-    const unsigned short* r0 = X + (long)perm[k] * Hp;
+    const unsigned short* r0 = X + (long)(perm ? perm[k] : k) * Hp;
     float f[8];
     unpack8(*reinterpret_cast<const uint4*>(r0 + lane * 8), f);
 #pragma unroll
@@ -829,30 +781,22 @@ __global__ void __launch_bounds__(256) k_segsum_rows(int N, int Hp, const int32_
   }
 }
 
-template <int NCB>
-static int32_t seg_launch(hipStream_t st, bool fwd, int N, const int32_t* ptr, const int32_t* perm, const char* X,
-                          const float* rvec, const float* wx, int H, float alpha, const float* v_in, float* out, long ldo,
-                          float* v_out) {
-  const unsigned grid = (unsigned)((N + 3) / 4);
-  if (fwd) k_seg_fwd_w<NCB><<<grid, 256, 0, st>>>(N, ptr, X, rvec, wx, H, alpha, v_in, out, v_out);
-  else k_segsum_w<NCB><<<grid, 256, 0, st>>>(N, ptr, perm, X, out, ldo);
-  HGNN_LAUNCH_CHECK("wide segment kernel");
-  return HGNN_OK;
-}
-static int32_t launch_seg_w(hipStream_t st, int tag, bool fwd, int Hp, int N, const int32_t* ptr, const int32_t* perm,
-                            const char* X, const float* rvec, const float* wx, int H, float alpha, const float* v_in,
-                            float* out, long ldo, float* v_out) {
+static int32_t launch_seg_fwd_w(hipStream_t st, int Hp, int N, const int32_t* row_ptr, const char* z2_T, const float* rvec,
+                                const float* wx, int H, float alpha, const float* v_in, float* M, float* v_out) {
   if (N <= 0) return HGNN_OK;
-  ProfScope ps(tag, st);
+  ProfScope ps(PT_SEG_FWD, st);
+  const unsigned grid = (unsigned)((N + 3) / 4);
   switch (Hp / 32) {
-    case 12: return seg_launch<12>(st, fwd, N, ptr, perm, X, rvec, wx, H, alpha, v_in, out, ldo, v_out);
-    case 16: return seg_launch<16>(st, fwd, N, ptr, perm, X, rvec, wx, H, alpha, v_in, out, ldo, v_out);
-    case 20: return seg_launch<20>(st, fwd, N, ptr, perm, X, rvec, wx, H, alpha, v_in, out, ldo, v_out);
-    case 24: return seg_launch<24>(st, fwd, N, ptr, perm, X, rvec, wx, H, alpha, v_in, out, ldo, v_out);
-    case 28: return seg_launch<28>(st, fwd, N, ptr, perm, X, rvec, wx, H, alpha, v_in, out, ldo, v_out);
-    case 32: return seg_launch<32>(st, fwd, N, ptr, perm, X, rvec, wx, H, alpha, v_in, out, ldo, v_out);
+    case 12: k_seg_fwd_w<12><<<grid, 256, 0, st>>>(N, row_ptr, z2_T, rvec, wx, H, alpha, v_in, M, v_out); break;
+    case 16: k_seg_fwd_w<16><<<grid, 256, 0, st>>>(N, row_ptr, z2_T, rvec, wx, H, alpha, v_in, M, v_out); break;
+    case 20: k_seg_fwd_w<20><<<grid, 256, 0, st>>>(N, row_ptr, z2_T, rvec, wx, H, alpha, v_in, M, v_out); break;
+    case 24: k_seg_fwd_w<24><<<grid, 256, 0, st>>>(N, row_ptr, z2_T, rvec, wx, H, alpha, v_in, M, v_out); break;
+    case 28: k_seg_fwd_w<28><<<grid, 256, 0, st>>>(N, row_ptr, z2_T, rvec, wx, H, alpha, v_in, M, v_out); break;
+    case 32: k_seg_fwd_w<32><<<grid, 256, 0, st>>>(N, row_ptr, z2_T, rvec, wx, H, alpha, v_in, M, v_out); break;
+    default: return set_error(HGNN_ERR_BAD_SHAPE, "padded width %d is not supported", Hp);
   }
-  return set_error(HGNN_ERR_BAD_SHAPE, "padded width %d is not supported", Hp);
+  HGNN_LAUNCH_CHECK("k_seg_fwd_w");
+  return HGNN_OK;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -896,6 +840,8 @@ struct WideSaved {
   char* z2_T;
   float* M;             // [Np, Hp] fp32 row-major
   float* z3;            // [Np, Hp]
+  char* hM_T;           // [Np, 2 Hp] T fragments of [h ; M]     (operands of the reverse pass's weight gradients)
+  char* a3_T;           // [Np, Hp] T fragments of silu(z3)
   size_t bytes;
 };
 static WideSaved carve_saved_w(void* p, const WideDims& d) {
@@ -907,6 +853,8 @@ static WideSaved carve_saved_w(void* p, const WideDims& d) {
   s.z2_T = c.take<char>(d.edge_bytes());
   s.M = c.take<float>((size_t)d.Np * d.Hp);
   s.z3 = c.take<float>((size_t)d.Np * d.Hp);
+  s.hM_T = c.take<char>(d.node_frag_bytes(2));
+  s.a3_T = c.take<char>(d.node_frag_bytes(1));
   s.bytes = c.used();
   return s;
 }
@@ -914,10 +862,8 @@ static WideSaved carve_saved_w(void* p, const WideDims& d) {
 struct WideWs {
   unsigned short* packed;   // 6 Hp^2 bf16 (the forward or the transposed set)
   char* hM_R;               // [Np, 2 Hp] R fragments of [h ; M]
-  char* hM_T;               // the same as T fragments
   char* x_R;                // [Np, 2 Hp] scratch R operand (a3, g_h', g_z3, g_PQ)
   char* x_T;                // [Np, 2 Hp] scratch T operand
-  char* a3_T;               // [Np, Hp]
   float* nodeA;             // [Np, 2 Hp] fp32 (g_a3, then g_hM)
   unsigned short* gM_b;     // [Np, 2 Hp] bf16 row-major copy of g_hM
   float* g_PQ;              // [Np, 2 Hp] fp32
@@ -936,10 +882,8 @@ static WideWs carve_ws_w(void* p, const WideDims& d) {
   WideWs w;
   w.packed = c.take<unsigned short>((size_t)6 * d.Hp * d.Hp);
   w.hM_R = c.take<char>(d.node_frag_bytes(2));
-  w.hM_T = c.take<char>(d.node_frag_bytes(2));
   w.x_R = c.take<char>(d.node_frag_bytes(2));
   w.x_T = c.take<char>(d.node_frag_bytes(2));
-  w.a3_T = c.take<char>(d.node_frag_bytes(1));
   w.nodeA = c.take<float>((size_t)d.Np * 2 * d.Hp);
   w.gM_b = c.take<unsigned short>((size_t)d.Np * 2 * d.Hp);
   w.g_PQ = c.take<float>((size_t)d.Np * 2 * d.Hp);
@@ -1052,25 +996,20 @@ int32_t wide_layer_fwd(hipStream_t st, const WideLayerArgs& a) {
   {
     PackFragArgs pk;
     pk.src = W; pk.K = H; pk.Nn = H; pk.Kp = Hp; pk.Np = Hp;
-    pk.dst = w.packed; pk.nkb_total = d.nkb; pk.nparts = 2;
-    pk.part[0] = {o.W1, H, 1, 0, 0};
-    pk.part[1] = {o.W1 + HH, H, 1, 0, d.ncb};
-    HGNN_TRY(launch_pack_frag(st, pk));
-    pk.dst = w.packed + 2 * PP; pk.nparts = 1;
-    pk.part[0] = {o.W2, H, 1, 0, 0};
-    HGNN_TRY(launch_pack_frag(st, pk));
-    pk.dst = w.packed + 3 * PP; pk.nkb_total = 2 * d.nkb; pk.nparts = 2;
-    pk.part[0] = {o.W3, H, 1, 0, 0};
-    pk.part[1] = {o.W3 + HH, H, 1, d.nkb, 0};
-    HGNN_TRY(launch_pack_frag(st, pk));
-    pk.dst = w.packed + 5 * PP; pk.nkb_total = d.nkb; pk.nparts = 1;
-    pk.part[0] = {o.W4, H, 1, 0, 0};
+    pk.dst = w.packed; pk.nparts = 6;
+    pk.part[0] = {o.W1, H, 1, 0, d.nkb, 0, 0};
+    pk.part[1] = {o.W1 + HH, H, 1, 0, d.nkb, 0, d.ncb};
+    pk.part[2] = {o.W2, H, 1, 2 * PP, d.nkb, 0, 0};
+    pk.part[3] = {o.W3, H, 1, 3 * PP, 2 * d.nkb, 0, 0};
+    pk.part[4] = {o.W3 + HH, H, 1, 3 * PP, 2 * d.nkb, d.nkb, 0};
+    pk.part[5] = {o.W4, H, 1, 5 * PP, d.nkb, 0, 0};
     HGNN_TRY(launch_pack_frag(st, pk));
   }
   {  // h -> first half of the [h ; M] operand
     ToFragArgs t;
     t.X = a.h_in; t.ldx = H; t.M = d.N; t.Mp = d.Np; t.ncol = H; t.Cp = Hp;
     t.R = w.hM_R; t.r_nkb = 2 * d.nkb; t.r_kb0 = 0;
+    t.T = s.hM_T; t.t_ncb = 2 * d.ncb; t.t_cb0 = 0;
     HGNN_TRY(launch_to_frag(st, t));
   }
   {  // P | Q = h [W1a | W1b] + [b1 | 0], bf16 row-major for the edge gathers
@@ -1097,12 +1036,12 @@ int32_t wide_layer_fwd(hipStream_t st, const WideLayerArgs& a) {
     g.bias = W + o.b2; g.nbias = H;
     HGNN_TRY(launch_fgemm_rows_T(st, g));
   }
-  HGNN_TRY(launch_seg_w(st, PT_SEG_FWD, true, Hp, d.N, a.row_ptr, nullptr, s.z2_T, a.rvec, W + o.wx, H, a.alpha, a.v_in,
-                        s.M, Hp, a.v_out));
+  HGNN_TRY(launch_seg_fwd_w(st, Hp, d.N, a.row_ptr, s.z2_T, a.rvec, W + o.wx, H, a.alpha, a.v_in, s.M, a.v_out));
   {  // M -> second half of the [h ; M] operand
     ToFragArgs t;
     t.X = s.M; t.ldx = Hp; t.M = d.N; t.Mp = d.Np; t.ncol = Hp; t.Cp = Hp;
     t.R = w.hM_R; t.r_nkb = 2 * d.nkb; t.r_kb0 = d.nkb;
+    t.T = s.hM_T; t.t_ncb = 2 * d.ncb; t.t_cb0 = d.ncb;
     HGNN_TRY(launch_to_frag(st, t));
   }
   {  // z3 = [h ; M] W3 + b3
@@ -1115,6 +1054,7 @@ int32_t wide_layer_fwd(hipStream_t st, const WideLayerArgs& a) {
     ToFragArgs t;
     t.X = s.z3; t.ldx = Hp; t.mode = 1; t.M = d.N; t.Mp = d.Np; t.ncol = H; t.Cp = Hp;
     t.R = w.x_R; t.r_nkb = d.nkb; t.r_kb0 = 0;
+    t.T = s.a3_T; t.t_ncb = d.ncb; t.t_cb0 = 0;
     HGNN_TRY(launch_to_frag(st, t));
   }
   {  // h' = h + a3 W4 + b4
@@ -1142,35 +1082,17 @@ int32_t wide_layer_bwd(hipStream_t st, const WideLayerArgs& a) {
   {
     PackFragArgs pk;
     pk.src = W; pk.K = H; pk.Nn = H; pk.Kp = Hp; pk.Np = Hp;
-    pk.dst = w.packed; pk.nkb_total = d.nkb; pk.nparts = 1;
-    pk.part[0] = {o.W4, 1, H, 0, 0};
-    HGNN_TRY(launch_pack_frag(st, pk));
-    pk.dst = w.packed + PP; pk.nparts = 2;
-    pk.part[0] = {o.W3, 1, H, 0, 0};
-    pk.part[1] = {o.W3 + HH, 1, H, 0, d.ncb};
-    HGNN_TRY(launch_pack_frag(st, pk));
-    pk.dst = w.packed + 3 * PP; pk.nparts = 1;
-    pk.part[0] = {o.W2, 1, H, 0, 0};
-    HGNN_TRY(launch_pack_frag(st, pk));
-    pk.dst = w.packed + 4 * PP; pk.nkb_total = 2 * d.nkb; pk.nparts = 2;
-    pk.part[0] = {o.W1, 1, H, 0, 0};
-    pk.part[1] = {o.W1 + HH, 1, H, d.nkb, 0};
+    pk.dst = w.packed; pk.nparts = 6;
+    pk.part[0] = {o.W4, 1, H, 0, d.nkb, 0, 0};
+    pk.part[1] = {o.W3, 1, H, PP, d.nkb, 0, 0};
+    pk.part[2] = {o.W3 + HH, 1, H, PP, d.nkb, 0, d.ncb};
+    pk.part[3] = {o.W2, 1, H, 3 * PP, d.nkb, 0, 0};
+    pk.part[4] = {o.W1, 1, H, 4 * PP, 2 * d.nkb, 0, 0};
+    pk.part[5] = {o.W1 + HH, 1, H, 4 * PP, 2 * d.nkb, d.nkb, 0};
     HGNN_TRY(launch_pack_frag(st, pk));
   }
   // operands of the atom-level products
-  {  // [h ; M] as T fragments
-    ToFragArgs t;
-    t.X = a.h_in; t.ldx = H; t.M = d.N; t.Mp = d.Np; t.ncol = H; t.Cp = Hp;
-    t.T = w.hM_T; t.t_ncb = 2 * d.ncb; t.t_cb0 = 0;
-    HGNN_TRY(launch_to_frag(st, t));
-    t.X = s.M; t.ldx = Hp; t.ncol = Hp; t.t_cb0 = d.ncb;
-    HGNN_TRY(launch_to_frag(st, t));
-  }
-  {  // a3 = silu(z3) as T, g_h' as R and T
-    ToFragArgs t;
-    t.X = s.z3; t.ldx = Hp; t.mode = 1; t.M = d.N; t.Mp = d.Np; t.ncol = H; t.Cp = Hp;
-    t.T = w.a3_T; t.t_ncb = d.ncb; t.t_cb0 = 0;
-    HGNN_TRY(launch_to_frag(st, t));
+  {  // g_h' as R and T ([h ; M] and silu(z3) were left as T fragments by the forward pass)
     ToFragArgs u;
     u.X = a.g_h_out; u.ldx = H; u.M = d.N; u.Mp = d.Np; u.ncol = H; u.Cp = Hp;
     u.R = w.x_R; u.r_nkb = d.nkb; u.r_kb0 = 0;
@@ -1178,7 +1100,7 @@ int32_t wide_layer_bwd(hipStream_t st, const WideLayerArgs& a) {
     HGNN_TRY(launch_to_frag(st, u));
   }
   // g_W4 = a3^T g_h', g_b4 = column sums of g_h'
-  HGNN_TRY(wgrad_w(st, d, w.a3_T, d.ncb, 0, d.ncb, w.x_T, d.ncb, 0, d.ncb, d.Np, w.partial, w.partial_floats, gW + o.W4,
+  HGNN_TRY(wgrad_w(st, d, s.a3_T, d.ncb, 0, d.ncb, w.x_T, d.ncb, 0, d.ncb, d.Np, w.partial, w.partial_floats, gW + o.W4,
                    0, 0, PT_WGRAD_NODE));
   HGNN_TRY(colsum_w(st, a.g_h_out, H, nullptr, 0, 0, d.N, H, w.cs_partial, gW + o.b4));
   {  // g_a3 = g_h' W4^T
@@ -1195,7 +1117,7 @@ int32_t wide_layer_bwd(hipStream_t st, const WideLayerArgs& a) {
     HGNN_TRY(colsum_w(st, w.nodeA, Hp, s.z3, Hp, 2, d.N, H, w.cs_partial, gW + o.b3));
   }
   // g_W3 = [h ; M]^T g_z3
-  HGNN_TRY(wgrad_w(st, d, w.hM_T, 2 * d.ncb, 0, 2 * d.ncb, w.x_T, d.ncb, 0, d.ncb, d.Np, w.partial, w.partial_floats,
+  HGNN_TRY(wgrad_w(st, d, s.hM_T, 2 * d.ncb, 0, 2 * d.ncb, w.x_T, d.ncb, 0, d.ncb, d.Np, w.partial, w.partial_floats,
                    gW + o.W3, HH, 0, PT_WGRAD_NODE));
   {  // [g_h(a) | g_M] = g_z3 [W3a^T | W3b^T]: fp32 for the residual, bf16 for the edge gathers
     FGemmArgs g = nn_args(w.x_R, d.nkb, d.Np / 32, w.packed + PP, 2 * d.ncb, PT_GEMM_NODE);
@@ -1242,8 +1164,11 @@ int32_t wide_layer_bwd(hipStream_t st, const WideLayerArgs& a) {
     HGNN_TRY(launch_reduce_cols(st, w.colpart + Hp, eg, 2 * Hp, H, gW + o.W1 + 2 * HH));
   }
   // g_P, g_Q: per-atom sums of g_z1 over the destination-sorted and the source-sorted lists
-  HGNN_TRY(launch_seg_w(st, PT_SEGSUM_DST, false, Hp, d.N, a.row_ptr, nullptr, w.ga1_T, nullptr, nullptr, H, 0.f, nullptr,
-                        w.g_PQ, 2 * Hp, nullptr));
+  if (d.N > 0) {
+    ProfScope ps(PT_SEGSUM_DST, st);
+    k_segsum_rows<<<(unsigned)((d.N + 3) / 4), 256, 0, st>>>(d.N, Hp, a.row_ptr, nullptr, e.gz1_rm, w.g_PQ, 2 * Hp);
+    HGNN_LAUNCH_CHECK("k_segsum_rows");
+  }
   if (d.N > 0) {
     ProfScope ps(PT_SEGSUM_SRC, st);
     k_segsum_rows<<<(unsigned)((d.N + 3) / 4), 256, 0, st>>>(d.N, Hp, a.colT_ptr, a.permT, e.gz1_rm, w.g_PQ + Hp, 2 * Hp);
@@ -1257,7 +1182,7 @@ int32_t wide_layer_bwd(hipStream_t st, const WideLayerArgs& a) {
     HGNN_TRY(launch_to_frag(st, t));
   }
   // g_W1a = h^T g_P, g_W1b = h^T g_Q
-  HGNN_TRY(wgrad_w(st, d, w.hM_T, 2 * d.ncb, 0, d.ncb, w.x_T, 2 * d.ncb, 0, 2 * d.ncb, d.Np, w.partial, w.partial_floats,
+  HGNN_TRY(wgrad_w(st, d, s.hM_T, 2 * d.ncb, 0, d.ncb, w.x_T, 2 * d.ncb, 0, 2 * d.ncb, d.Np, w.partial, w.partial_floats,
                    gW + o.W1, 0, HH, PT_WGRAD_NODE));
   {  // g_h = g_h' + g_h(a) + [g_P | g_Q] [W1a^T ; W1b^T]
     FGemmArgs g = nn_args(w.x_R, 2 * d.nkb, d.Np / 32, w.packed + 4 * PP, d.ncb, PT_GEMM_NODE);
