@@ -11,6 +11,7 @@
 #include "edge_fused.h"
 #include "edgeops.h"
 #include "gemm.h"
+#include "side.h"
 #include "wide.h"
 
 namespace hgnn {
@@ -94,12 +95,7 @@ static LayerWs carve_ws(void* p, int N, int64_t E, int H, bool bf16) {
 // Weight gradients are off the critical path of the reverse pass (nothing downstream reads them), so they run
 // on a library-owned side stream (default priority) that forks from and joins the caller's stream through
 // events: they overlap the latency-bound kernels of the main chain. Everything stays asynchronous to the host.
-struct SideStream {
-  hipStream_t s = nullptr;
-  hipEvent_t ev[8] = {};
-  bool ok = false;
-};
-static SideStream& side_stream() {
+SideStream& side_stream() {
   static SideStream ss;
   if (!ss.ok) {
     bool good = hipStreamCreateWithFlags(&ss.s, hipStreamNonBlocking) == hipSuccess;
@@ -109,7 +105,7 @@ static SideStream& side_stream() {
   return ss;
 }
 // `to` waits for everything enqueued on `from` so far
-static int32_t stream_after(hipStream_t to, hipStream_t from, hipEvent_t ev) {
+int32_t stream_after(hipStream_t to, hipStream_t from, hipEvent_t ev) {
   HGNN_HIP(hipEventRecord(ev, from));
   HGNN_HIP(hipStreamWaitEvent(to, ev, 0));
   return HGNN_OK;
@@ -117,7 +113,7 @@ static int32_t stream_after(hipStream_t to, hipStream_t from, hipEvent_t ev) {
 
 // -1: not decided yet (then the environment variable HGNN_SIDE_STREAM decides: "0" = off); 0 / 1: set by the caller
 static int g_side_mode = -1;
-static bool side_stream_enabled() {
+bool side_stream_enabled() {
   if (g_side_mode < 0) {
     const char* e = getenv("HGNN_SIDE_STREAM");
     g_side_mode = (e && e[0] == '0') ? 0 : 1;

@@ -15,6 +15,7 @@
 
 #include "devmath.h"
 #include "frag.h"
+#include "side.h"
 #include "edge_fused.h"
 #include "edgeops.h"
 
@@ -863,15 +864,19 @@ struct WideWs {
   unsigned short* packed;   // 6 Hp^2 bf16 (the forward or the transposed set)
   char* hM_R;               // [Np, 2 Hp] R fragments of [h ; M]
   char* x_R;                // [Np, 2 Hp] scratch R operand (a3, g_h', g_z3, g_PQ)
-  char* x_T;                // [Np, 2 Hp] scratch T operand
-  float* nodeA;             // [Np, 2 Hp] fp32 (g_a3, then g_hM)
+  char* gh_T;               // [Np, Hp] T operands of the weight gradients (read on the side stream: each its own)
+  char* gz3_T;              // [Np, Hp]
+  char* gPQ_T;              // [Np, 2 Hp]
+  float* nodeA;             // [Np, Hp] fp32 g_a3
+  float* nodeB;             // [Np, 2 Hp] fp32 g_hM
   unsigned short* gM_b;     // [Np, 2 Hp] bf16 row-major copy of g_hM
   float* g_PQ;              // [Np, 2 Hp] fp32
   char* gz2_R;              // [Ep, Hp]
   char* gz2_T;
   char* ga1_T;
   float* cvec;              // [E]
-  float* colpart;           // ELEM_MAX_BLOCKS x 2 x Hp
+  float* colpart;           // ELEM_MAX_BLOCKS x 2 x Hp (g_z2 kernel)
+  float* colpart2;          // the same for the g_z1 kernel
   float* cs_partial;        // column sums over atoms
   float* partial;           // split partials of the weight-gradient products
   size_t partial_floats;
@@ -883,8 +888,11 @@ static WideWs carve_ws_w(void* p, const WideDims& d) {
   w.packed = c.take<unsigned short>((size_t)6 * d.Hp * d.Hp);
   w.hM_R = c.take<char>(d.node_frag_bytes(2));
   w.x_R = c.take<char>(d.node_frag_bytes(2));
-  w.x_T = c.take<char>(d.node_frag_bytes(2));
-  w.nodeA = c.take<float>((size_t)d.Np * 2 * d.Hp);
+  w.gh_T = c.take<char>(d.node_frag_bytes(1));
+  w.gz3_T = c.take<char>(d.node_frag_bytes(1));
+  w.gPQ_T = c.take<char>(d.node_frag_bytes(2));
+  w.nodeA = c.take<float>((size_t)d.Np * d.Hp);
+  w.nodeB = c.take<float>((size_t)d.Np * 2 * d.Hp);
   w.gM_b = c.take<unsigned short>((size_t)d.Np * 2 * d.Hp);
   w.g_PQ = c.take<float>((size_t)d.Np * 2 * d.Hp);
   w.gz2_R = c.take<char>(d.edge_bytes());
@@ -892,6 +900,7 @@ static WideWs carve_ws_w(void* p, const WideDims& d) {
   w.ga1_T = c.take<char>(d.edge_bytes());
   w.cvec = c.take<float>((size_t)d.E + 4);
   w.colpart = c.take<float>((size_t)ELEM_MAX_BLOCKS * 2 * d.Hp);
+  w.colpart2 = c.take<float>((size_t)ELEM_MAX_BLOCKS * 2 * d.Hp);
   w.cs_partial = c.take<float>(colsum_rows_partial_floats(d.N, d.Hp, 1));
   w.partial_floats = (size_t)24 * 2 * d.Hp * d.Hp;
   w.partial = c.take<float>(w.partial_floats);
@@ -1091,37 +1100,43 @@ int32_t wide_layer_bwd(hipStream_t st, const WideLayerArgs& a) {
     pk.part[5] = {o.W1 + HH, 1, H, 4 * PP, 2 * d.nkb, d.nkb, 0};
     HGNN_TRY(launch_pack_frag(st, pk));
   }
-  // operands of the atom-level products
+  // Weight gradients and bias sums feed nothing downstream: they run on the library's side stream (sx), which forks
+  // from and joins the caller's stream through events. Buffers read on sx are written once per call on st.
+  SideStream& ss = side_stream();
+  HGNN_REQUIRE(ss.ok, HGNN_ERR_HIP, "could not create the side stream");
+  hipStream_t sx = side_stream_enabled() ? ss.s : st;
   {  // g_h' as R and T ([h ; M] and silu(z3) were left as T fragments by the forward pass)
     ToFragArgs u;
     u.X = a.g_h_out; u.ldx = H; u.M = d.N; u.Mp = d.Np; u.ncol = H; u.Cp = Hp;
     u.R = w.x_R; u.r_nkb = d.nkb; u.r_kb0 = 0;
-    u.T = w.x_T; u.t_ncb = d.ncb; u.t_cb0 = 0;
+    u.T = w.gh_T; u.t_ncb = d.ncb; u.t_cb0 = 0;
     HGNN_TRY(launch_to_frag(st, u));
   }
-  // g_W4 = a3^T g_h', g_b4 = column sums of g_h'
-  HGNN_TRY(wgrad_w(st, d, s.a3_T, d.ncb, 0, d.ncb, w.x_T, d.ncb, 0, d.ncb, d.Np, w.partial, w.partial_floats, gW + o.W4,
+  HGNN_TRY(stream_after(sx, st, ss.ev[0]));
+  // side: g_W4 = a3^T g_h', g_b4 = column sums of g_h'
+  HGNN_TRY(wgrad_w(sx, d, s.a3_T, d.ncb, 0, d.ncb, w.gh_T, d.ncb, 0, d.ncb, d.Np, w.partial, w.partial_floats, gW + o.W4,
                    0, 0, PT_WGRAD_NODE));
-  HGNN_TRY(colsum_w(st, a.g_h_out, H, nullptr, 0, 0, d.N, H, w.cs_partial, gW + o.b4));
+  HGNN_TRY(colsum_w(sx, a.g_h_out, H, nullptr, 0, 0, d.N, H, w.cs_partial, gW + o.b4));
   {  // g_a3 = g_h' W4^T
     FGemmArgs g = nn_args(w.x_R, d.nkb, d.Np / 32, w.packed, d.ncb, PT_GEMM_NODE);
     g.M = d.N; g.Cf = w.nodeA; g.ldc = Hp; g.ncol_f = Hp;
     HGNN_TRY(launch_fgemm_rows(st, g));
   }
-  {  // g_z3 = g_a3 silu'(z3) as R and T; g_b3 = its column sums
+  {  // g_z3 = g_a3 silu'(z3) as R and T
     ToFragArgs t;
     t.X = w.nodeA; t.ldx = Hp; t.Z = s.z3; t.ldz = Hp; t.mode = 2; t.M = d.N; t.Mp = d.Np; t.ncol = H; t.Cp = Hp;
     t.R = w.x_R; t.r_nkb = d.nkb; t.r_kb0 = 0;
-    t.T = w.x_T; t.t_ncb = d.ncb; t.t_cb0 = 0;
+    t.T = w.gz3_T; t.t_ncb = d.ncb; t.t_cb0 = 0;
     HGNN_TRY(launch_to_frag(st, t));
-    HGNN_TRY(colsum_w(st, w.nodeA, Hp, s.z3, Hp, 2, d.N, H, w.cs_partial, gW + o.b3));
   }
-  // g_W3 = [h ; M]^T g_z3
-  HGNN_TRY(wgrad_w(st, d, s.hM_T, 2 * d.ncb, 0, 2 * d.ncb, w.x_T, d.ncb, 0, d.ncb, d.Np, w.partial, w.partial_floats,
+  HGNN_TRY(stream_after(sx, st, ss.ev[1]));
+  // side: g_b3 = column sums of g_z3, g_W3 = [h ; M]^T g_z3
+  HGNN_TRY(colsum_w(sx, w.nodeA, Hp, s.z3, Hp, 2, d.N, H, w.cs_partial, gW + o.b3));
+  HGNN_TRY(wgrad_w(sx, d, s.hM_T, 2 * d.ncb, 0, 2 * d.ncb, w.gz3_T, d.ncb, 0, d.ncb, d.Np, w.partial, w.partial_floats,
                    gW + o.W3, HH, 0, PT_WGRAD_NODE));
   {  // [g_h(a) | g_M] = g_z3 [W3a^T | W3b^T]: fp32 for the residual, bf16 for the edge gathers
     FGemmArgs g = nn_args(w.x_R, d.nkb, d.Np / 32, w.packed + PP, 2 * d.ncb, PT_GEMM_NODE);
-    g.M = d.N; g.Cf = w.nodeA; g.ldc = 2 * Hp; g.ncol_f = 2 * Hp;
+    g.M = d.N; g.Cf = w.nodeB; g.ldc = 2 * Hp; g.ncol_f = 2 * Hp;
     g.Cb = w.gM_b; g.ldcb = 2 * Hp;
     HGNN_TRY(launch_fgemm_rows(st, g));
   }
@@ -1140,28 +1155,24 @@ int32_t wide_layer_bwd(hipStream_t st, const WideLayerArgs& a) {
     k_edge_elem<EE_GZ2><<<egrid, 256, 0, st>>>(e);
     HGNN_LAUNCH_CHECK("k_edge_elem (g_z2)");
   }
-  {
-    ProfScope ps(PT_COLSUM, st);
-    HGNN_TRY(launch_reduce_cols(st, w.colpart, eg, 2 * Hp, H, gW + o.b2));
-    HGNN_TRY(launch_reduce_cols(st, w.colpart + Hp, eg, 2 * Hp, H, gW + o.wx));
+  HGNN_TRY(stream_after(sx, st, ss.ev[2]));
+  {  // side: g_b2, g_wx from the kernel's column sums; g_W2 = a1^T g_z2
+    ProfScope ps(PT_COLSUM, sx);
+    HGNN_TRY(launch_reduce_cols(sx, w.colpart, eg, 2 * Hp, H, gW + o.b2));
+    HGNN_TRY(launch_reduce_cols(sx, w.colpart + Hp, eg, 2 * Hp, H, gW + o.wx));
   }
-  // g_W2 = a1^T g_z2
-  HGNN_TRY(wgrad_w(st, d, s.a1_T, d.ncb, 0, d.ncb, w.gz2_T, d.ncb, 0, d.ncb, d.Ep, w.partial, w.partial_floats,
+  HGNN_TRY(wgrad_w(sx, d, s.a1_T, d.ncb, 0, d.ncb, w.gz2_T, d.ncb, 0, d.ncb, d.Ep, w.partial, w.partial_floats,
                    gW + o.W2, 0, 0, PT_FRAG_WGRAD_EDGE));
   if (d.Ep > 0) {  // g_a1 = g_z2 W2^T (T fragments)
     FGemmArgs g = nn_args(w.gz2_R, d.nkb, (int)(d.Ep / 32), w.packed + 3 * PP, d.ncb, PT_FRAG_GEMM_EDGE);
     g.T = w.ga1_T; g.t_ncb = d.ncb;
     HGNN_TRY(launch_fgemm_rows_T(st, g));
   }
+  e.colpart = w.colpart2;
   {
     ProfScope ps(PT_EDGE_ELEM, st);
     k_edge_elem<EE_GZ1><<<egrid, 256, 0, st>>>(e);
     HGNN_LAUNCH_CHECK("k_edge_elem (g_z1)");
-  }
-  {
-    ProfScope ps(PT_COLSUM, st);
-    HGNN_TRY(launch_reduce_cols(st, w.colpart, eg, 2 * Hp, H, gW + o.b1));
-    HGNN_TRY(launch_reduce_cols(st, w.colpart + Hp, eg, 2 * Hp, H, gW + o.W1 + 2 * HH));
   }
   // g_P, g_Q: per-atom sums of g_z1 over the destination-sorted and the source-sorted lists
   if (d.N > 0) {
@@ -1178,19 +1189,25 @@ int32_t wide_layer_bwd(hipStream_t st, const WideLayerArgs& a) {
     ToFragArgs t;
     t.X = w.g_PQ; t.ldx = 2 * Hp; t.M = d.N; t.Mp = d.Np; t.ncol = 2 * Hp; t.Cp = 2 * Hp;
     t.R = w.x_R; t.r_nkb = 2 * d.nkb; t.r_kb0 = 0;
-    t.T = w.x_T; t.t_ncb = 2 * d.ncb; t.t_cb0 = 0;
+    t.T = w.gPQ_T; t.t_ncb = 2 * d.ncb; t.t_cb0 = 0;
     HGNN_TRY(launch_to_frag(st, t));
   }
-  // g_W1a = h^T g_P, g_W1b = h^T g_Q
-  HGNN_TRY(wgrad_w(st, d, s.hM_T, 2 * d.ncb, 0, d.ncb, w.x_T, 2 * d.ncb, 0, 2 * d.ncb, d.Np, w.partial, w.partial_floats,
+  HGNN_TRY(stream_after(sx, st, ss.ev[3]));
+  {  // side: g_b1, g_w1d from the g_z1 kernel's column sums; g_W1a = h^T g_P, g_W1b = h^T g_Q
+    ProfScope ps(PT_COLSUM, sx);
+    HGNN_TRY(launch_reduce_cols(sx, w.colpart2, eg, 2 * Hp, H, gW + o.b1));
+    HGNN_TRY(launch_reduce_cols(sx, w.colpart2 + Hp, eg, 2 * Hp, H, gW + o.W1 + 2 * HH));
+  }
+  HGNN_TRY(wgrad_w(sx, d, s.hM_T, 2 * d.ncb, 0, d.ncb, w.gPQ_T, 2 * d.ncb, 0, 2 * d.ncb, d.Np, w.partial, w.partial_floats,
                    gW + o.W1, 0, HH, PT_WGRAD_NODE));
   {  // g_h = g_h' + g_h(a) + [g_P | g_Q] [W1a^T ; W1b^T]
     FGemmArgs g = nn_args(w.x_R, 2 * d.nkb, d.Np / 32, w.packed + 4 * PP, d.ncb, PT_GEMM_NODE);
     g.M = d.N; g.Cf = a.g_h_in; g.ldc = H; g.ncol_f = H;
     g.r1 = a.g_h_out; g.ld1 = H;
-    g.r2 = w.nodeA; g.ld2 = 2 * Hp;
+    g.r2 = w.nodeB; g.ld2 = 2 * Hp;
     HGNN_TRY(launch_fgemm_rows(st, g));
   }
+  HGNN_TRY(stream_after(st, sx, ss.ev[4]));   // join: the caller's stream now also orders after every gradient
   if (a.g_v_in != a.g_v_out) HGNN_TRY(launch_copy_f32(st, a.g_v_out, a.g_v_in, (int64_t)d.N * 3));
   return HGNN_OK;
 }

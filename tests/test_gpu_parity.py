@@ -263,14 +263,20 @@ def test_step_is_bitwise_reproducible():
         assert np.array_equal(a.view(np.uint32), c.view(np.uint32))
 
 
-def test_side_stream_on_and_off_give_the_same_bits():
+def _paper_shape_small():
+    b = small_mixed_batch(11, n_mol=5, n_cry=4, S=3, mol_atoms=(3, 40), cry_atoms=(2, 30))
+    return problem_from_batch(b, 4.5, 866, 2, 3, "bf16", seed=866, Hh=889, D=3)
+
+
+@pytest.mark.parametrize("which", ["cfg3", "paper-shape"])
+def test_side_stream_on_and_off_give_the_same_bits(which):
     """Weight gradients run on the library's side stream by default; keeping them on the caller's stream must not
     change a single bit (the sums have a fixed order either way). cfg3: bf16 pairs, i.e. the recomputing W2-gradient
-    kernel with both of its launches (whole blocks, left-over and ragged blocks)."""
-    say("side stream on/off")
+    kernel with both of its launches (whole blocks, left-over and ragged blocks); paper-shape: the fragment path."""
+    say("side stream on/off", which)
     import torch
     from paper_2506_21788_amd import binding as B
-    P = problem_from_config("cfg3")
+    P = problem_from_config("cfg3") if which == "cfg3" else _paper_shape_small()
     outs = []
     before = B.set_side_stream(True)
     try:
@@ -289,13 +295,13 @@ def test_side_stream_on_and_off_give_the_same_bits():
             assert np.array_equal(a.view(np.uint32), c.view(np.uint32))
 
 
-@pytest.mark.parametrize("name", ["cfg1", "cfg3"])
+@pytest.mark.parametrize("name", ["cfg1", "cfg3", "paper-shape"])
 def test_hip_graph_replays_match_eager_bitwise(name):
     """forward + backward recorded into a HIP graph: every replay, with eager work and synchronisations between
     the replays, gives the bits of the eager step."""
     say(f"hip graph {name}")
     import torch
-    P = problem_from_config(name)
+    P = _paper_shape_small() if name == "paper-shape" else problem_from_config(name)
     gE, gF = torch.as_tensor(P["gE"]).cuda(), torch.as_tensor(P["gF"]).cuda()
     hpth = gpu_hotpath(P)
     hpth.build_graph()
@@ -423,9 +429,7 @@ def test_reduced_cfg5_backward():
 # ------------------------------------------------------------------------------------------------
 def test_step_small_mixed_paper_shape():
     say("step small mixed, H = 866, heads 3 x 889")
-    b = small_mixed_batch(11, n_mol=5, n_cry=4, S=3, mol_atoms=(3, 40), cry_atoms=(2, 30))
-    P = problem_from_batch(b, 4.5, 866, 2, 3, "bf16", seed=866, Hh=889, D=3)
-    compare_step(P, "small H=866 Hh=889 D=3 bf16")
+    compare_step(_paper_shape_small(), "small H=866 Hh=889 D=3 bf16")
 
 
 def test_full_size_cfg6_sampled_graphs():
