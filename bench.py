@@ -54,8 +54,9 @@ def kernel_work(tag, N, E, H, dtype):
         return 2.0 * EH * H, 2 * EH * b + 2.0 * H * H
     if tag == "frag_wgrad_edge":     # in: a1, g_z2; out: H x H
         return 2.0 * EH * H, 2 * EH * b + 4.0 * H * H
-    if tag == "edge_elementwise":    # three kernels per layer; on average ~3 edge tensors moved per launch
-        return 0.0, 3 * EH * b + 12.0 * E + 2 * NH * b
+    if tag == "edge_elementwise":    # three kernels per layer: a1 (out 2 copies), g_z2 (in z2, out 2 copies), g_z1 (in g_a1,
+        # out 1 copy) = 7 edge tensors, 36 B of per-edge scalars and 5 gathered atom tensors over 3 launches
+        return 0.0, (7 * EH * b + 36.0 * E + 5 * NH * b) / 3.0
     if tag.startswith("neigh"):      # whole graph build: in pos; out col, shift, d2, rvec, dst, permT, offsets
         return 0.0, 12.0 * N + 31.0 * E + 12.0 * N
     return 0.0, 0.0

@@ -100,7 +100,7 @@ int32_t hgnn_radius_graph_fill(void* stream, int32_t N, int32_t G,
  * Embedding: h0[i,:] = emb[Z[i],:]  (input node features = learnable table indexed by atomic
  * number, 0 <= Z <= HGNN_ZMAX). _bwd: g_emb[z,:] = sum over atoms with Z == z of g_h[i,:], summed in
  * atom order (chunks of atoms are reduced first, then the chunks in order); ws is scratch of
- * hgnn_embed_bwd_workspace_bytes(N, H) bytes.
+ * hgnn_embed_bwd_workspace_bytes(N, H) bytes. 1 <= H <= 1024 (vector kernels at 64 / 128 / 256).
  * ------------------------------------------------------------------------------------------- */
 int32_t hgnn_embed_fwd(void* stream, int32_t N, int32_t H, const int32_t* Z,
                        const float* emb /*[ZMAX+1,H]*/, float* h /*out [N,H]*/);
@@ -160,6 +160,7 @@ int32_t hgnn_mp_layer_bwd(void* stream, int32_t N, int64_t E, int32_t H, int32_t
  * Pooling over the contiguous atoms of each graph: p_g = sum or mean of h_i (mean gives the
  * "energy per atom" target of the paper its per-atom normalisation). Empty graphs give 0.
  * _bwd: g_h_i (+)= g_p[g(i)] (/ n_g);  accumulate != 0 adds into g_h instead of overwriting it.
+ * 1 <= H <= 1024.
  * ------------------------------------------------------------------------------------------- */
 int32_t hgnn_pool_by_graph_fwd(void* stream, int32_t N, int32_t G, int32_t H, int32_t mode,
                                const int32_t* graph_off, const float* h, float* p /*out [G,H]*/);
