@@ -39,19 +39,20 @@ __device__ __forceinline__ float bf_hi(unsigned w) { return __uint_as_float(w & 
 // ---------------------------------------------------------------------------------------------
 // fragment GEMM
 // ---------------------------------------------------------------------------------------------
-template <int WI, int WJ>
+// NW wavefronts per workgroup, arranged (NW / 2) x 2 over the tile; each owns WI x WJ blocks of 32 x 32
+template <int WI, int WJ, int NW = 4>
 struct FCfg {
   static constexpr int KC = 2;               // contraction blocks staged per step
-  static constexpr int TI = 2 * WI, TJ = 2 * WJ;
+  static constexpr int TI = (NW / 2) * WI, TJ = 2 * WJ;
   static constexpr int NF = KC * (TI + TJ);  // fragments per step
-  static constexpr int PASSES = NF / 4;      // each wavefront copies one fragment per pass
+  static constexpr int PASSES = NF / NW;     // each wavefront copies one fragment per pass
   static constexpr int LDS_BYTES = 2 * NF * 1024;   // two steps: one being multiplied, one being written
-  static_assert(NF % 4 == 0, "fragments per step must divide among four wavefronts");
+  static_assert(NF % NW == 0, "fragments per step must divide among the wavefronts");
 };
 
-template <int WI, int WJ, int EPI>
-__global__ void __launch_bounds__(256, (WI * WJ <= 8 ? 2 : 1)) k_fgemm(FGemmArgs p) {
-  using C = FCfg<WI, WJ>;
+template <int WI, int WJ, int EPI, int NW = 4>
+__global__ void __launch_bounds__(64 * NW, (WI * WJ <= 8 ? 2 : 1)) k_fgemm(FGemmArgs p) {
+  using C = FCfg<WI, WJ, NW>;
   extern __shared__ __align__(16) u32x4_t lds[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -99,7 +100,7 @@ __global__ void __launch_bounds__(256, (WI * WJ <= 8 ? 2 : 1)) k_fgemm(FGemmArgs
   long kst[C::PASSES];
 #pragma unroll
   for (int s = 0; s < C::PASSES; ++s) {
-    const int f = 4 * s + wave;
+    const int f = NW * s + wave;
     if (f < C::KC * C::TI) {
       const int kk = f / C::TI, ii = f % C::TI;
       src[s] = p.A + ((long)(i0 + ii) * p.a_si + (long)kk * p.a_sk) * 1024 + lane * 16;
@@ -137,7 +138,7 @@ __global__ void __launch_bounds__(256, (WI * WJ <= 8 ? 2 : 1)) k_fgemm(FGemmArgs
 #pragma unroll
       for (int s = 0; s < C::PASSES; ++s) preY[s] = *reinterpret_cast<const u32x4_t*>(src[s] + k1 * kst[s]);
 #pragma unroll
-      for (int s = 0; s < C::PASSES; ++s) lds[(4 * s + wave) * 64 + lane] = preX[s];
+      for (int s = 0; s < C::PASSES; ++s) lds[(NW * s + wave) * 64 + lane] = preX[s];
 #pragma unroll
       for (int s = 0; s < C::PASSES; ++s) preX[s] = *reinterpret_cast<const u32x4_t*>(src[s] + k2 * kst[s]);
     }
@@ -169,12 +170,12 @@ __global__ void __launch_bounds__(256, (WI * WJ <= 8 ? 2 : 1)) k_fgemm(FGemmArgs
           const long kn = kclamp(cc + 3);
           if (par == 0) {
 #pragma unroll
-            for (int s = 0; s < C::PASSES; ++s) lds[nslot * STAGE + (4 * s + wave) * 64 + lane] = preY[s];
+            for (int s = 0; s < C::PASSES; ++s) lds[nslot * STAGE + (NW * s + wave) * 64 + lane] = preY[s];
 #pragma unroll
             for (int s = 0; s < C::PASSES; ++s) preY[s] = *reinterpret_cast<const u32x4_t*>(src[s] + kn * kst[s]);
           } else {
 #pragma unroll
-            for (int s = 0; s < C::PASSES; ++s) lds[nslot * STAGE + (4 * s + wave) * 64 + lane] = preX[s];
+            for (int s = 0; s < C::PASSES; ++s) lds[nslot * STAGE + (NW * s + wave) * 64 + lane] = preX[s];
 #pragma unroll
             for (int s = 0; s < C::PASSES; ++s) preX[s] = *reinterpret_cast<const u32x4_t*>(src[s] + kn * kst[s]);
           }
@@ -234,9 +235,9 @@ __global__ void __launch_bounds__(256, (WI * WJ <= 8 ? 2 : 1)) k_fgemm(FGemmArgs
   }
 }
 
-template <int WI, int WJ, int EPI>
+template <int WI, int WJ, int EPI, int NW = 4>
 static int32_t launch_fgemm_t(hipStream_t st, const FGemmArgs& a) {
-  using C = FCfg<WI, WJ>;
+  using C = FCfg<WI, WJ, NW>;
   HGNN_REQUIRE(a.nI % C::TI == 0 && (a.nJ % C::TJ == 0 || EPI != EPI_PART) && a.nkb % C::KC == 0 &&
                    a.kper % C::KC == 0 && a.kper > 0,
                HGNN_ERR_BAD_SHAPE, "fragment GEMM: %d x %d blocks, %d contraction blocks do not tile", a.nI, a.nJ, a.nkb);
@@ -249,12 +250,12 @@ static int32_t launch_fgemm_t(hipStream_t st, const FGemmArgs& a) {
   HGNN_REQUIRE(gx <= 2147483647L && groups <= 65535, HGNN_ERR_OVERFLOW, "fragment GEMM: grid too large");
   static bool lds_set = false;   // the ring may exceed the default dynamic LDS limit: raise it once per variant
   if (!lds_set) {
-    HGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_fgemm<WI, WJ, EPI>),
+    HGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_fgemm<WI, WJ, EPI, NW>),
                                  hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES));
     lds_set = true;
   }
   ProfScope ps(a.tag, st);
-  k_fgemm<WI, WJ, EPI><<<dim3((unsigned)gx, 1, groups), 256, C::LDS_BYTES, st>>>(a);
+  k_fgemm<WI, WJ, EPI, NW><<<dim3((unsigned)gx, 1, groups), 64 * NW, C::LDS_BYTES, st>>>(a);
   HGNN_LAUNCH_CHECK("k_fgemm");
   return HGNN_OK;
 }
@@ -966,8 +967,8 @@ int32_t launch_fgemm_rows(hipStream_t st, const FGemmArgs& a) {
   if (big_tiles < 4L * num_cus()) return launch_fgemm_t<2, 2, EPI_ROW>(st, a);
   return launch_fgemm_t<4, 2, EPI_ROW>(st, a);
 }
-// (256 x 256 tiles, one workgroup of four wavefronts per CU, move a third less through the L2 but measured 15 % slower
-// than two resident 256 x 128 workgroups)
+// (256 x 256 tiles move a third less through the L2 but measured slower than two resident 256 x 128 workgroups of four
+// wavefronts: by 15 % with one workgroup of four wavefronts per CU, by 6 % with one of eight, NW = 8 below)
 int32_t launch_fgemm_rows_T(hipStream_t st, const FGemmArgs& a) { return launch_fgemm_t<4, 2, EPI_T>(st, a); }
 
 // layer-level shorthand: square Hp blocks, no groups

@@ -71,3 +71,46 @@ def _run(G, atoms, H, Hh, D, S, seed, sources=None):
 ])
 def test_deep_heads_match_the_oracle(G, atoms, H, Hh, D, S, sources):
     _run(G, atoms, H, Hh, D, S, seed=G + H + D, sources=sources)
+
+
+def test_deep_heads_and_wide_layer_error_paths():
+    """Argument errors come back as status codes from the host side; nothing is launched for them."""
+    import torch
+    from paper_2506_21788_amd import binding as B
+    N, G, H, Hh, D, S = 20, 3, 300, 280, 2, 2
+    f32 = dict(dtype=torch.float32, device="cuda")
+    graph_off = torch.tensor([0, 7, 12, 20], dtype=torch.int32, device="cuda")
+    src = torch.tensor([0, 1, 0], dtype=torch.int32, device="cuda")
+    plan = torch.empty(B.multihead_plan_ints(N, G, S), dtype=torch.int32, device="cuda")
+    B.multihead_plan(N, G, S, graph_off, src, plan)
+    ws_b, sv_b = B.multihead_deep_workspace_bytes(N, G, H, Hh, D, S, B.BF16)
+    ws = torch.empty(ws_b, dtype=torch.uint8, device="cuda")
+    sv = torch.empty(sv_b, dtype=torch.uint8, device="cuda")
+    from hgnn_inputs import deep_head_weight_count
+    Wh = torch.zeros(S * deep_head_weight_count(H, Hh, D), **f32)
+    p, h, v = torch.zeros((G, H), **f32), torch.zeros((N, H), **f32), torch.zeros((N, 3), **f32)
+    e, f = torch.empty(G, **f32), torch.empty((N, 3), **f32)
+
+    def code(call):
+        with pytest.raises(B.HgnnError) as err:
+            call()
+        return err.value.code
+
+    assert code(lambda: B.multihead_deep_fwd(N, G, H, Hh, D, S, B.BF16, plan, p, h, v, Wh, e, f, sv, ws[:1024])) == -6
+    assert code(lambda: B.multihead_deep_fwd(N, G, H, Hh, D, S, B.BF16, plan, p, h, v, Wh, e, f, sv[:64], ws)) == -6
+    assert code(lambda: B.multihead_deep_fwd(N, G, H, Hh, D, S, B.BF16, plan, p, None, v, Wh, e, f, sv, ws)) == -1
+    assert code(lambda: B.multihead_deep_fwd(N, G, H, Hh, 9, S, B.BF16, plan, p, h, v, Wh, e, f, sv, ws)) == -2
+    assert code(lambda: B.multihead_deep_fwd(N, G, H, Hh, D, S, B.F32, plan, p, h, v, Wh, e, f, sv, ws)) == -9
+    B.multihead_deep_fwd(N, G, H, Hh, D, S, B.BF16, plan, p, h, v, Wh, e, f, sv, ws)   # the good call still works
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(e).all())
+    # the layer above H = 256: float32 operands are not implemented, small buffers are refused
+    assert code(lambda: B.mp_layer_workspace_bytes(N, 50, 300, B.F32)) == -9
+    assert code(lambda: B.mp_layer_workspace_bytes(N, 50, 1025, B.BF16)) == -2
+    lws, lsv = B.mp_layer_workspace_bytes(N, 0, 300, B.BF16)
+    W = torch.zeros(6 * 300 * 300 + 6 * 300, **f32)
+    row_ptr = torch.zeros(N + 1, dtype=torch.int32, device="cuda")
+    h300, out = torch.zeros((N, 300), **f32), torch.empty((N, 300), **f32)
+    assert code(lambda: B.mp_layer_fwd(N, 0, 300, B.BF16, 1.0, row_ptr, None, None, None, None, h300, v, W, out, f,
+                                       torch.empty(lsv, dtype=torch.uint8, device="cuda"),
+                                       torch.empty(64, dtype=torch.uint8, device="cuda"))) == -6
