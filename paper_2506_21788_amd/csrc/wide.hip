@@ -4,7 +4,7 @@
 //                  residuals (atom tensors), fp32 split partials (weight gradients)
 //   k_pack_frag    fp32 weight slices -> B fragments (zero padded)
 //   k_to_frag      row-major fp32 atom tensor -> R and / or T fragments (optionally silu(x) or x * silu'(z))
-//   k_edge_elem    the three element-wise edge kernels on 32 x 64 tiles: a1 = silu(P[dst] + Q[col] + d2 w1d) -> R, T;
+//   k_edge_elem    the three element-wise edge kernels on 32 x 128 tiles: a1 = silu(P[dst] + Q[col] + d2 w1d) -> R, T;
 //                  g_z2 = (alpha g_M[dst] + c_e wx) silu'(z2) -> R, T (+ column sums for g_b2, g_wx);
 //                  g_z1 = g_a1 silu'(z1) -> row-major (+ column sums for g_b1, g_w1d)
 //   k_seg_fwd_w    M_i = alpha sum silu(z2), v'_i = v_i + alpha sum (wx . m_e) rvec_e   (one wavefront per atom)
@@ -40,9 +40,9 @@ __device__ __forceinline__ float bf_hi(unsigned w) { return __uint_as_float(w & 
 // fragment GEMM
 // ---------------------------------------------------------------------------------------------
 // NW wavefronts per workgroup, arranged (NW / 2) x 2 over the tile; each owns WI x WJ blocks of 32 x 32
-template <int WI, int WJ, int NW = 4>
+template <int WI, int WJ, int NW = 4, int KC_ = 2>
 struct FCfg {
-  static constexpr int KC = 2;               // contraction blocks staged per step
+  static constexpr int KC = KC_;             // contraction blocks staged per step
   static constexpr int TI = (NW / 2) * WI, TJ = 2 * WJ;
   static constexpr int NF = KC * (TI + TJ);  // fragments per step
   static constexpr int PASSES = NF / NW;     // each wavefront copies one fragment per pass
@@ -50,9 +50,9 @@ struct FCfg {
   static_assert(NF % NW == 0, "fragments per step must divide among the wavefronts");
 };
 
-template <int WI, int WJ, int EPI, int NW = 4>
+template <int WI, int WJ, int EPI, int NW = 4, int KC = 2>
 __global__ void __launch_bounds__(64 * NW, (WI * WJ <= 8 ? 2 : 1)) k_fgemm(FGemmArgs p) {
-  using C = FCfg<WI, WJ, NW>;
+  using C = FCfg<WI, WJ, NW, KC>;
   extern __shared__ __align__(16) u32x4_t lds[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -235,9 +235,9 @@ __global__ void __launch_bounds__(64 * NW, (WI * WJ <= 8 ? 2 : 1)) k_fgemm(FGemm
   }
 }
 
-template <int WI, int WJ, int EPI, int NW = 4>
+template <int WI, int WJ, int EPI, int NW = 4, int KC = 2>
 static int32_t launch_fgemm_t(hipStream_t st, const FGemmArgs& a) {
-  using C = FCfg<WI, WJ, NW>;
+  using C = FCfg<WI, WJ, NW, KC>;
   HGNN_REQUIRE(a.nI % C::TI == 0 && (a.nJ % C::TJ == 0 || EPI != EPI_PART) && a.nkb % C::KC == 0 &&
                    a.kper % C::KC == 0 && a.kper > 0,
                HGNN_ERR_BAD_SHAPE, "fragment GEMM: %d x %d blocks, %d contraction blocks do not tile", a.nI, a.nJ, a.nkb);
@@ -250,12 +250,12 @@ static int32_t launch_fgemm_t(hipStream_t st, const FGemmArgs& a) {
   HGNN_REQUIRE(gx <= 2147483647L && groups <= 65535, HGNN_ERR_OVERFLOW, "fragment GEMM: grid too large");
   static bool lds_set = false;   // the ring may exceed the default dynamic LDS limit: raise it once per variant
   if (!lds_set) {
-    HGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_fgemm<WI, WJ, EPI, NW>),
+    HGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_fgemm<WI, WJ, EPI, NW, KC>),
                                  hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES));
     lds_set = true;
   }
   ProfScope ps(a.tag, st);
-  k_fgemm<WI, WJ, EPI, NW><<<dim3((unsigned)gx, 1, groups), 64 * NW, C::LDS_BYTES, st>>>(a);
+  k_fgemm<WI, WJ, EPI, NW, KC><<<dim3((unsigned)gx, 1, groups), 64 * NW, C::LDS_BYTES, st>>>(a);
   HGNN_LAUNCH_CHECK("k_fgemm");
   return HGNN_OK;
 }
@@ -478,13 +478,15 @@ __global__ void __launch_bounds__(256) k_reduce_wgrad(const float* __restrict__ 
 }
 
 // ---------------------------------------------------------------------------------------------
-// element-wise edge kernels. A workgroup walks tiles of 32 edges (one row block) x 64 columns:
+// element-wise edge kernels. A workgroup walks tiles of 32 edges (one row block) x 128 columns:
 //   compute mapping, thread (q, x) = (tid >> 6, tid & 63): the 8 edges of row set (row group 2 rb32 + (q >> 1), lane
-//     half q & 1) in column 64 slab + x. T fragments are loaded and stored in this mapping: a wavefront moves two
-//     contiguous half fragments with one 16-byte access per lane.
-//   R mapping (through an LDS copy of the tile), thread (q, x): contraction block 4 slab + q, lane x of the fragment
-//     (row x & 31, 8 columns from 8 (x >> 5)): a wavefront stores one whole 1 KiB fragment.
-// Every global store instruction therefore writes whole cache lines.
+//     half q & 1) in the column pair 128 slab + 2 x, + 1. T fragments are loaded and stored in this mapping (32 bytes
+//     per lane, a wavefront moves four contiguous half fragments); a gather fetches both columns with one 4-byte load
+//     (the vector memory pipe takes one address per lane whatever the width: 2-byte gathers made these kernels
+//     address-bound).
+//   R mapping (through an LDS copy of the tile), wavefront q: contraction blocks 8 slab + 2 q, + 1, lane x of the
+//     fragment (row x & 31, 8 columns from 8 (x >> 5)): one whole 1 KiB fragment per store instruction.
+// Every global store instruction writes whole cache lines.
 // ---------------------------------------------------------------------------------------------
 struct EdgeElemArgs {
   int64_t E = 0;
@@ -523,145 +525,142 @@ __device__ __forceinline__ uint4 pack8(const float (&f)[8]) {
 }
 
 enum { EE_A1 = 0, EE_GZ2 = 1, EE_GZ1 = 2 };
-constexpr int EE_PITCH = 72;   // LDS tile row pitch in bf16 elements (64 + 8: 16-byte reads of a column of rows spread over the banks)
+constexpr int EE_PITCH = 136;   // LDS tile row pitch in bf16 elements (128 + 8: 16-byte reads of a column of rows spread over the banks)
 
 // EE_A1:  a1 = silu(P[dst] + Q[col] + d2 w1d)                                   -> R and T
 // EE_GZ2: g_z2 = (alpha g_M[dst] + c_e wx) silu'(z2)                            -> R and T; sums: g_b2 = sum g_z2, g_wx = sum c_e silu(z2)
 // EE_GZ1: g_z1 = g_a1 silu'(z1), z1 recomputed from the gathers                 -> row-major; sums: g_b1 = sum g_z1, g_w1d = sum d2 g_z1
-constexpr int EE_U = 1;   // tiles in flight per workgroup: all their loads are issued before the first is used
 template <int MODE>
 __global__ void __launch_bounds__(256) k_edge_elem(EdgeElemArgs p) {
-  __shared__ __align__(16) unsigned short tile[EE_U][32 * EE_PITCH];
-  __shared__ float csum[4][2][64];
+  __shared__ __align__(16) unsigned short tile[32 * EE_PITCH];
+  __shared__ float csum[4][2][128];
   const int tid = threadIdx.x, x = tid & 63;
   const int q = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int slab = blockIdx.x;
-  const int c = slab * 64 + x;
+  const int c = slab * 128 + 2 * x;       // this thread's columns: c, c + 1
   const int ncb = p.Hp >> 5, nkb = p.Hp >> 4;
   const int hh = q >> 1, g = q & 1;
-  const float wcol = c < p.H ? (MODE == EE_GZ2 ? p.wx[c] : p.w1d[c]) : 0.f;   // wx or w1d of this thread's column
+  const float* wv = MODE == EE_GZ2 ? p.wx : p.w1d;
+  const float w0 = c < p.H ? wv[c] : 0.f, w1 = c + 1 < p.H ? wv[c + 1] : 0.f;
   const long lastrow = p.E > 0 ? p.E - 1 : 0;
   char* Tdst = MODE == EE_A1 ? p.a1_T : p.gz2_T;
-  float s0 = 0.f, s1 = 0.f;
-  for (int rb0 = blockIdx.y; rb0 < p.nrb; rb0 += EE_U * gridDim.y) {
-    // ---- loads of up to EE_U tiles (row blocks rb0 + t gridDim.y; blocks past the end are clamped and not stored)
-    u32x4_t tin[EE_U];
-    unsigned short ga[EE_U][8], gb[EE_U][8];
-    float sc[EE_U][8], sd[EE_U][8];
+  float s00 = 0.f, s01 = 0.f, s10 = 0.f, s11 = 0.f;   // [sum][column]
+  for (int rb = blockIdx.y; rb < p.nrb; rb += gridDim.y) {
+    const int rb16 = 2 * rb + hh;
+    // the two columns are neighbouring 16-byte slots of one half fragment
+    const long tfrag = ((long)rb16 * ncb + (c >> 5)) * 1024 + (g * 32 + (c & 31)) * 16;
+    u32x4_t in0, in1;
+    if (MODE == EE_GZ2) {
+      in0 = *reinterpret_cast<const u32x4_t*>(p.z2_T + tfrag);
+      in1 = *reinterpret_cast<const u32x4_t*>(p.z2_T + tfrag + 16);
+    }
+    if (MODE == EE_GZ1) {
+      in0 = *reinterpret_cast<const u32x4_t*>(p.ga1_T + tfrag);
+      in1 = *reinterpret_cast<const u32x4_t*>(p.ga1_T + tfrag + 16);
+    }
+    unsigned ga[8], gb[8];
+    float sc[8];
+    bool ok[8];
 #pragma unroll
-    for (int t = 0; t < EE_U; ++t) {
-      const int rbt = rb0 + t * (int)gridDim.y;
-      const int rb = rbt < p.nrb ? rbt : p.nrb - 1;
-      const int rb16 = 2 * rb + hh;
-      const long tfrag = ((long)rb16 * ncb + (c >> 5)) * 1024 + (g * 32 + (c & 31)) * 16;
-      if (MODE == EE_GZ2) tin[t] = *reinterpret_cast<const u32x4_t*>(p.z2_T + tfrag);
-      if (MODE == EE_GZ1) tin[t] = *reinterpret_cast<const u32x4_t*>(p.ga1_T + tfrag);
+    for (int u = 0; u < 8; ++u) {
+      const long r = tset_row(rb16, g, u);     // the same for all lanes of the wavefront
+      ok[u] = r < p.E;
+      const long rr = ok[u] ? r : lastrow;
+      const long di = p.dst[rr];
+      if (MODE == EE_GZ2) {
+        sc[u] = p.cvec[rr];
+        ga[u] = *reinterpret_cast<const unsigned*>(p.gM + di * p.ldgM + c);
+      } else {
+        const long ci = p.col[rr];
+        sc[u] = p.d2[rr];
+        ga[u] = *reinterpret_cast<const unsigned*>(p.PQ + di * 2 * p.Hp + c);
+        gb[u] = *reinterpret_cast<const unsigned*>(p.PQ + ci * 2 * p.Hp + p.Hp + c);
+      }
+    }
+    float o0[8], o1[8];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        const long r = tset_row(rb16, g, u);     // the same for all lanes of the wavefront
-        const long rr = r < p.E ? r : lastrow;
-        const long di = p.dst[rr];
-        if (MODE == EE_GZ2) {
-          sc[t][u] = p.cvec[rr];
-          ga[t][u] = p.gM[di * p.ldgM + c];
+    for (int u = 0; u < 8; ++u) {
+      const unsigned i0w = MODE == EE_A1 ? 0u : in0[u >> 1], i1w = MODE == EE_A1 ? 0u : in1[u >> 1];
+      const float x0 = (u & 1) ? bf_hi(i0w) : bf_lo(i0w), x1 = (u & 1) ? bf_hi(i1w) : bf_lo(i1w);
+      if (MODE == EE_GZ2) {
+        float y0, d0, y1, d1;
+        silu_both(x0, y0, d0);
+        silu_both(x1, y1, d1);
+        const float gz0 = ok[u] ? fmaf(sc[u], w0, p.alpha * bf_lo(ga[u])) * d0 : 0.f;
+        const float gz1 = ok[u] ? fmaf(sc[u], w1, p.alpha * bf_hi(ga[u])) * d1 : 0.f;
+        s00 += gz0; s01 += gz1;
+        s10 += ok[u] ? sc[u] * y0 : 0.f;
+        s11 += ok[u] ? sc[u] * y1 : 0.f;
+        o0[u] = gz0; o1[u] = gz1;
+      } else {
+        const float z0 = bf_lo(ga[u]) + bf_lo(gb[u]) + sc[u] * w0;
+        const float z1 = bf_hi(ga[u]) + bf_hi(gb[u]) + sc[u] * w1;
+        if (MODE == EE_A1) {
+          o0[u] = ok[u] ? silu_f(z0) : 0.f;
+          o1[u] = ok[u] ? silu_f(z1) : 0.f;
         } else {
-          const long ci = p.col[rr];
-          sd[t][u] = p.d2[rr];
-          ga[t][u] = p.PQ[di * 2 * p.Hp + c];
-          gb[t][u] = p.PQ[ci * 2 * p.Hp + p.Hp + c];
+          const float gz0 = ok[u] ? x0 * dsilu_f(z0) : 0.f;
+          const float gz1 = ok[u] ? x1 * dsilu_f(z1) : 0.f;
+          s00 += gz0; s01 += gz1;
+          s10 += ok[u] ? sc[u] * gz0 : 0.f;
+          s11 += ok[u] ? sc[u] * gz1 : 0.f;
+          o0[u] = gz0; o1[u] = gz1;
         }
       }
     }
-    // ---- arithmetic and the T stores
-    u32x4_t packed[EE_U];
+    if (MODE != EE_GZ1) {   // g_z1 is only read row by row: it goes out row-major below
+      u32x4_t t0, t1;
 #pragma unroll
-    for (int t = 0; t < EE_U; ++t) {
-      const int rbt = rb0 + t * (int)gridDim.y;
-      const bool live = rbt < p.nrb;
-      const int rb16 = 2 * rbt + hh;
-      float in[8], out[8];
-      if (MODE != EE_A1) {
-        const unsigned w4[4] = {tin[t][0], tin[t][1], tin[t][2], tin[t][3]};
-#pragma unroll
-        for (int u = 0; u < 8; ++u) in[u] = (u & 1) ? bf_hi(w4[u >> 1]) : bf_lo(w4[u >> 1]);
+      for (int k = 0; k < 4; ++k) {
+        t0[k] = pack_bf16x2(o0[2 * k], o0[2 * k + 1]);
+        t1[k] = pack_bf16x2(o1[2 * k], o1[2 * k + 1]);
       }
-#pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        const bool ok = live && tset_row(rb16, g, u) < p.E;
-        if (MODE == EE_GZ2) {
-          float y, dy;
-          silu_both(in[u], y, dy);
-          const float gz = ok ? fmaf(sc[t][u], wcol, p.alpha * bf_lo(ga[t][u])) * dy : 0.f;
-          s0 += gz;
-          s1 += ok ? sc[t][u] * y : 0.f;
-          out[u] = gz;
-        } else {
-          const float z = bf_lo(ga[t][u]) + bf_lo(gb[t][u]) + sd[t][u] * wcol;
-          if (MODE == EE_A1) {
-            out[u] = ok ? silu_f(z) : 0.f;
-          } else {
-            const float gz = ok ? in[u] * dsilu_f(z) : 0.f;
-            s0 += gz;
-            s1 += ok ? sd[t][u] * gz : 0.f;
-            out[u] = gz;
-          }
-        }
-      }
-      packed[t][0] = pack_bf16x2(out[0], out[1]);
-      packed[t][1] = pack_bf16x2(out[2], out[3]);
-      packed[t][2] = pack_bf16x2(out[4], out[5]);
-      packed[t][3] = pack_bf16x2(out[6], out[7]);
-      if (live && MODE != EE_GZ1) {   // g_z1 is only read row by row: it goes out row-major below
-        const long tfrag = ((long)rb16 * ncb + (c >> 5)) * 1024 + (g * 32 + (c & 31)) * 16;
-        *reinterpret_cast<u32x4_t*>(Tdst + tfrag) = packed[t];
-      }
+      *reinterpret_cast<u32x4_t*>(Tdst + tfrag) = t0;
+      *reinterpret_cast<u32x4_t*>(Tdst + tfrag + 16) = t1;
     }
-    // ---- the tiles in row-major order for the second mapping (rows of this row set: 16 hh + 8 (u >> 2) + 4 g + (u & 3))
-    __syncthreads();   // the previous tiles have been read
+    // the tile in row-major order for the second mapping (rows of this row set: 16 hh + 8 (u >> 2) + 4 g + (u & 3))
+    __syncthreads();   // the previous tile has been read
 #pragma unroll
-    for (int t = 0; t < EE_U; ++t) {
-      const unsigned w4[4] = {packed[t][0], packed[t][1], packed[t][2], packed[t][3]};
-#pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        const int lr = 16 * hh + 8 * (u >> 2) + 4 * g + (u & 3);
-        tile[t][lr * EE_PITCH + x] = (unsigned short)((u & 1) ? (w4[u >> 1] >> 16) : (w4[u >> 1] & 0xffffu));
-      }
+    for (int u = 0; u < 8; ++u) {
+      const int lr = 16 * hh + 8 * (u >> 2) + 4 * g + (u & 3);
+      *reinterpret_cast<unsigned*>(&tile[lr * EE_PITCH + 2 * x]) = pack_bf16x2(o0[u], o1[u]);
     }
     __syncthreads();
+    if (MODE == EE_GZ1) {
+      // row-major copy: 16 pieces of 16 bytes per tile row; thread -> row tid >> 4 (+ 16), piece tid & 15
 #pragma unroll
-    for (int t = 0; t < EE_U; ++t) {
-      const int rbt = rb0 + t * (int)gridDim.y;
-      if (rbt < p.nrb) {
-        if (MODE == EE_GZ1) {
-          // row-major copy: thread -> row tid >> 3, 16-byte piece tid & 7 of the tile's 128-byte row segment
-          const int lr = tid >> 3, pc = tid & 7;
-          const u32x4_t w = *reinterpret_cast<const u32x4_t*>(&tile[t][lr * EE_PITCH + pc * 8]);
-          *reinterpret_cast<u32x4_t*>(p.gz1_rm + ((long)rbt * 32 + lr) * p.Hp + slab * 64 + pc * 8) = w;
-        } else {
-          const int lr = x & 31, g2 = x >> 5;
-          const u32x4_t w = *reinterpret_cast<const u32x4_t*>(&tile[t][lr * EE_PITCH + q * 16 + g2 * 8]);
-          char* Rdst = MODE == EE_A1 ? p.a1_R : p.gz2_R;
-          *reinterpret_cast<u32x4_t*>(Rdst + (((long)rbt * nkb + 4 * slab + q) * 64 + x) * 16) = w;
-        }
+      for (int hrow = 0; hrow < 2; ++hrow) {
+        const int lr = (tid >> 4) + 16 * hrow, pc = tid & 15;
+        const u32x4_t w = *reinterpret_cast<const u32x4_t*>(&tile[lr * EE_PITCH + pc * 8]);
+        *reinterpret_cast<u32x4_t*>(p.gz1_rm + ((long)rb * 32 + lr) * p.Hp + slab * 128 + pc * 8) = w;
+      }
+    } else {
+      const int lr = x & 31, g2 = x >> 5;
+      char* Rdst = MODE == EE_A1 ? p.a1_R : p.gz2_R;
+#pragma unroll
+      for (int kb2 = 0; kb2 < 2; ++kb2) {
+        const int kbl = 2 * q + kb2;   // contraction block inside the tile
+        const u32x4_t w = *reinterpret_cast<const u32x4_t*>(&tile[lr * EE_PITCH + kbl * 16 + g2 * 8]);
+        *reinterpret_cast<u32x4_t*>(Rdst + (((long)rb * nkb + 8 * slab + kbl) * 64 + x) * 16) = w;
       }
     }
   }
   if (MODE != EE_A1) {
     // column sums of the workgroup: the four row sets are added in order
-    csum[q][0][x] = s0;
-    csum[q][1][x] = s1;
+    csum[q][0][2 * x] = s00; csum[q][0][2 * x + 1] = s01;
+    csum[q][1][2 * x] = s10; csum[q][1][2 * x + 1] = s11;
     __syncthreads();
-    if (q == 0) {
-      float* o = p.colpart + (long)blockIdx.y * 2 * p.Hp + c;
-      o[0] = ((csum[0][0][x] + csum[1][0][x]) + csum[2][0][x]) + csum[3][0][x];
-      o[p.Hp] = ((csum[0][1][x] + csum[1][1][x]) + csum[2][1][x]) + csum[3][1][x];
+    if (tid < 128) {
+      float* o = p.colpart + (long)blockIdx.y * 2 * p.Hp + slab * 128 + tid;
+      o[0] = ((csum[0][0][tid] + csum[1][0][tid]) + csum[2][0][tid]) + csum[3][0][tid];
+      o[p.Hp] = ((csum[0][1][tid] + csum[1][1][tid]) + csum[2][1][tid]) + csum[3][1][tid];
     }
   }
 }
 
-constexpr int ELEM_MAX_BLOCKS = 256;   // row-block phases (= column-sum partials) of the element-wise edge kernels
+constexpr int ELEM_MAX_BLOCKS = 512;   // row-block phases (= column-sum partials) of the element-wise edge kernels
 static dim3 elem_grid(int nrb, int Hp) {
-  return dim3(Hp / 64, nrb < 1 ? 1 : (nrb < ELEM_MAX_BLOCKS ? nrb : ELEM_MAX_BLOCKS));
+  return dim3(Hp / 128, nrb < 1 ? 1 : (nrb < ELEM_MAX_BLOCKS ? nrb : ELEM_MAX_BLOCKS));
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -879,8 +878,10 @@ struct WideWs {
   float* colpart;           // ELEM_MAX_BLOCKS x 2 x Hp (g_z2 kernel)
   float* colpart2;          // the same for the g_z1 kernel
   float* cs_partial;        // column sums over atoms
-  float* partial;           // split partials of the weight-gradient products
+  float* partial;           // split partials of the atom-level weight-gradient products (side stream)
   size_t partial_floats;
+  float* partial_e;         // split partials of g_W2 (caller's stream)
+  size_t partial_e_floats;
   size_t bytes;
 };
 static WideWs carve_ws_w(void* p, const WideDims& d) {
@@ -905,6 +906,8 @@ static WideWs carve_ws_w(void* p, const WideDims& d) {
   w.cs_partial = c.take<float>(colsum_rows_partial_floats(d.N, d.Hp, 1));
   w.partial_floats = (size_t)24 * 2 * d.Hp * d.Hp;
   w.partial = c.take<float>(w.partial_floats);
+  w.partial_e_floats = (size_t)24 * d.Hp * d.Hp;
+  w.partial_e = c.take<float>(w.partial_e_floats);
   w.bytes = c.used();
   return w;
 }
@@ -1157,12 +1160,13 @@ int32_t wide_layer_bwd(hipStream_t st, const WideLayerArgs& a) {
     HGNN_LAUNCH_CHECK("k_edge_elem (g_z2)");
   }
   HGNN_TRY(stream_after(sx, st, ss.ev[2]));
-  {  // side: g_b2, g_wx from the kernel's column sums; g_W2 = a1^T g_z2
+  {  // side: g_b2, g_wx from the kernel's column sums
     ProfScope ps(PT_COLSUM, sx);
     HGNN_TRY(launch_reduce_cols(sx, w.colpart, eg, 2 * Hp, H, gW + o.b2));
     HGNN_TRY(launch_reduce_cols(sx, w.colpart + Hp, eg, 2 * Hp, H, gW + o.wx));
   }
-  HGNN_TRY(wgrad_w(sx, d, s.a1_T, d.ncb, 0, d.ncb, w.gz2_T, d.ncb, 0, d.ncb, d.Ep, w.partial, w.partial_floats,
+  // g_W2 = a1^T g_z2 fills the chip by itself: it stays on the caller's stream, with a partial buffer of its own
+  HGNN_TRY(wgrad_w(st, d, s.a1_T, d.ncb, 0, d.ncb, w.gz2_T, d.ncb, 0, d.ncb, d.Ep, w.partial_e, w.partial_e_floats,
                    gW + o.W2, 0, 0, PT_FRAG_WGRAD_EDGE));
   if (d.Ep > 0) {  // g_a1 = g_z2 W2^T (T fragments)
     FGemmArgs g = nn_args(w.gz2_R, d.nkb, (int)(d.Ep / 32), w.packed + 3 * PP, d.ncb, PT_FRAG_GEMM_EDGE);
