@@ -426,7 +426,7 @@ static int32_t launch_reduce_cols(hipStream_t st, const float* partial, int nspl
   return HGNN_OK;
 }
 
-constexpr int CS_ROWS = 64;   // rows per partial of k_colsum_rows
+constexpr int CS_ROWS = 16;   // rows per partial of k_colsum_rows
 // partial[group][split][c] = sum over the split's rows of w * f(X[r][c])   (blockIdx.y: split, blockIdx.z: group)
 __global__ void __launch_bounds__(256) k_colsum_rows(ColsumRowsArgs a, int nsplit) {
   const int c = blockIdx.x * 256 + threadIdx.x;
