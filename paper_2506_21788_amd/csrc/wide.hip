@@ -288,96 +288,93 @@ int32_t launch_pack_frag(hipStream_t st, const PackFragArgs& a) {
 // ---------------------------------------------------------------------------------------------
 // row-major fp32 -> fragments.  mode 0: x, 1: silu(x), 2: x * silu'(z)
 // ---------------------------------------------------------------------------------------------
-// VEC: floats per load (the launcher picks 4 / 2 / 1 from the alignment of the sources)
-template <int VEC>
+// One workgroup per tile of 32 rows x 128 columns, in the two mappings of the element-wise edge kernels below:
+// compute mapping thread (q, x) = the 8 rows of one row set x the column pair 128 slab + 2 x, + 1 (T fragments leave
+// in this mapping, 32 bytes per lane), R fragments through an LDS copy of the tile (one whole fragment per store
+// instruction). VEC2: the column pair is read with one 8-byte load (the launcher checks the alignment).
+template <bool VEC2>
 __global__ void __launch_bounds__(256) k_to_frag(ToFragArgs a) {
-  const int CG = a.Cp >> 3;
-  const long idx = (long)blockIdx.x * 256 + threadIdx.x;
-  const int cg = (int)(idx % CG);
-  const long rs = idx / CG;   // row set of the group: 16-row group rs >> 1, lane half rs & 1
+  __shared__ __align__(16) unsigned short tile[32 * 136];
+  const int tid = threadIdx.x, x = tid & 63;
+  const int q = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int slab = blockIdx.x, rb = blockIdx.y;
   int pos0 = 0, pad0 = 0, n = a.M, npad = a.Mp;
   if (a.grp_ptr) {
-    group_range(a.grp_ptr, blockIdx.y, pos0, n, pad0);
+    group_range(a.grp_ptr, blockIdx.z, pos0, n, pad0);
     npad = (n + 255) / 256 * 256;
   }
-  if (rs >= npad / 8) return;
-  const int g = (int)(rs & 1);
-  const int c0 = cg * 8;
-  unsigned short vals[8][8];   // [u][k]
+  if (rb * 32 >= npad) return;   // uniform over the workgroup, before any barrier
+  const int hh = q >> 1, g = q & 1;
+  const int c = slab * 128 + 2 * x;
+  unsigned packed[8];   // [u]: columns c (low half), c + 1
 #pragma unroll
   for (int u = 0; u < 8; ++u) {
-    const int r = tset_row((int)(rs >> 1), g, u);
+    const int r = tset_row(2 * rb + hh, g, u);   // row inside the group
     const long sr = r < n ? (a.row_idx ? a.row_idx[pos0 + r] : pad0 + r) : 0;
-    typedef float vec_t __attribute__((ext_vector_type(VEC)));
-#pragma unroll
-    for (int k = 0; k < 8; k += VEC) {
-      float xv[VEC], zv[VEC];
-#pragma unroll
-      for (int t = 0; t < VEC; ++t) { xv[t] = 0.f; zv[t] = 0.f; }
-      // a whole vector is read where the row pitch covers it; single columns past ncol are zeroed below
-      if (r < n && c0 + k + VEC <= a.ldx && c0 + k < a.ncol) {
-        const vec_t x = *reinterpret_cast<const vec_t*>(a.X + sr * a.ldx + c0 + k);
-#pragma unroll
-        for (int t = 0; t < VEC; ++t) xv[t] = x[t];
+    float x0 = 0.f, x1 = 0.f, z0 = 0.f, z1 = 0.f;
+    if (r < n && c < a.ncol) {
+      // both columns are read where the row pitch covers them; a column past ncol is zeroed below
+      if (VEC2 && c + 2 <= a.ldx) {
+        const float2 xx = *reinterpret_cast<const float2*>(a.X + sr * a.ldx + c);
+        x0 = xx.x; x1 = xx.y;
         if (a.mode == 2) {
-          const vec_t zz = *reinterpret_cast<const vec_t*>(a.Z + sr * a.ldz + c0 + k);
-#pragma unroll
-          for (int t = 0; t < VEC; ++t) zv[t] = zz[t];
+          const float2 zz = *reinterpret_cast<const float2*>(a.Z + sr * a.ldz + c);
+          z0 = zz.x; z1 = zz.y;
+        }
+      } else {
+        x0 = a.X[sr * a.ldx + c];
+        if (a.mode == 2) z0 = a.Z[sr * a.ldz + c];
+        if (c + 1 < a.ncol) {
+          x1 = a.X[sr * a.ldx + c + 1];
+          if (a.mode == 2) z1 = a.Z[sr * a.ldz + c + 1];
         }
       }
-#pragma unroll
-      for (int t = 0; t < VEC; ++t) {
-        float v = xv[t];
-        if (a.mode == 1) v = silu_f(v);
-        else if (a.mode == 2) v *= dsilu_f(zv[t]);
-        if (c0 + k + t >= a.ncol) v = 0.f;
-        vals[u][k + t] = (unsigned short)f2bf_bits(v);
-      }
     }
+    if (a.mode == 1) { x0 = silu_f(x0); x1 = silu_f(x1); }
+    else if (a.mode == 2) { x0 *= dsilu_f(z0); x1 *= dsilu_f(z1); }
+    if (c + 1 >= a.ncol) x1 = 0.f;
+    if (c >= a.ncol) x0 = 0.f;
+    packed[u] = pack_bf16x2(x0, x1);
   }
-  const int rb16 = (int)(rs >> 1) + pad0 / 16;   // destination rows are the padded ones
+  if (a.T) {   // destination rows are the padded ones
+    const long rb16 = pad0 / 16 + 2 * rb + hh;
+    const long tfrag = ((rb16 * a.t_ncb + a.t_cb0 + (c >> 5)) * 64 + g * 32 + (c & 31)) * 16;
+    u32x4_t t0, t1;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      t0[k] = (packed[2 * k] & 0xffffu) | (packed[2 * k + 1] << 16);
+      t1[k] = (packed[2 * k] >> 16) | (packed[2 * k + 1] & 0xffff0000u);
+    }
+    *reinterpret_cast<u32x4_t*>(a.T + tfrag) = t0;
+    *reinterpret_cast<u32x4_t*>(a.T + tfrag + 16) = t1;
+  }
   if (a.R) {
 #pragma unroll
     for (int u = 0; u < 8; ++u) {
-      const int r = tset_row(rb16, g, u);
-      uint4 w;
-      w.x = vals[u][0] | ((unsigned)vals[u][1] << 16);
-      w.y = vals[u][2] | ((unsigned)vals[u][3] << 16);
-      w.z = vals[u][4] | ((unsigned)vals[u][5] << 16);
-      w.w = vals[u][6] | ((unsigned)vals[u][7] << 16);
-      const long frag = (long)(r >> 5) * a.r_nkb + a.r_kb0 + (c0 >> 4);
-      *reinterpret_cast<uint4*>(a.R + (frag * 64 + ((c0 >> 3) & 1) * 32 + (r & 31)) * 16) = w;
+      const int lr = 16 * hh + 8 * (u >> 2) + 4 * g + (u & 3);
+      *reinterpret_cast<unsigned*>(&tile[lr * 136 + 2 * x]) = packed[u];
     }
-  }
-  if (a.T) {
-    const long frag = (long)rb16 * a.t_ncb + a.t_cb0 + (c0 >> 5);
+    __syncthreads();
+    const int lr = x & 31, g2 = x >> 5;
 #pragma unroll
-    for (int k = 0; k < 8; ++k) {
-      uint4 w;
-      w.x = vals[0][k] | ((unsigned)vals[1][k] << 16);
-      w.y = vals[2][k] | ((unsigned)vals[3][k] << 16);
-      w.z = vals[4][k] | ((unsigned)vals[5][k] << 16);
-      w.w = vals[6][k] | ((unsigned)vals[7][k] << 16);
-      *reinterpret_cast<uint4*>(a.T + (frag * 64 + g * 32 + (c0 & 31) + k) * 16) = w;
+    for (int kb2 = 0; kb2 < 2; ++kb2) {
+      const int kbl = 2 * q + kb2;   // contraction block inside the tile
+      const u32x4_t w = *reinterpret_cast<const u32x4_t*>(&tile[lr * 136 + kbl * 16 + g2 * 8]);
+      const long frag = (long)(pad0 / 32 + rb) * a.r_nkb + a.r_kb0 + 8 * slab + kbl;
+      *reinterpret_cast<u32x4_t*>(a.R + (frag * 64 + x) * 16) = w;
     }
   }
 }
 
 int32_t launch_to_frag(hipStream_t st, const ToFragArgs& a) {
-  HGNN_REQUIRE(a.Mp % 256 == 0 && a.Cp % 32 == 0, HGNN_ERR_BAD_SHAPE, "to_frag: padded extents do not tile");
-  const long n = (long)(a.Mp / 8) * (a.Cp / 8);
-  if (n == 0) return HGNN_OK;
+  HGNN_REQUIRE(a.Mp % 256 == 0 && a.Cp % 128 == 0, HGNN_ERR_BAD_SHAPE, "to_frag: padded extents do not tile");
+  if (a.Mp == 0 || a.Cp == 0) return HGNN_OK;
+  HGNN_REQUIRE(a.Mp / 32 <= 65535, HGNN_ERR_OVERFLOW, "to_frag: too many rows");
   ProfScope ps(PT_TO_FRAG, st);
-  const dim3 grid((unsigned)((n + 255) / 256), a.grp_ptr ? a.S : 1);
-  auto fits = [&](int vec) {
-    const auto ok = [&](const float* p, long ld) {
-      return p == nullptr || (reinterpret_cast<uintptr_t>(p) % (4 * vec) == 0 && ld % vec == 0);
-    };
-    return ok(a.X, a.ldx) && (a.mode != 2 || ok(a.Z, a.ldz));
-  };
-  if (fits(4)) k_to_frag<4><<<grid, 256, 0, st>>>(a);
-  else if (fits(2)) k_to_frag<2><<<grid, 256, 0, st>>>(a);
-  else k_to_frag<1><<<grid, 256, 0, st>>>(a);
+  const dim3 grid(a.Cp / 128, a.Mp / 32, a.grp_ptr ? a.S : 1);
+  const auto even = [](const float* p, long ld) { return p == nullptr || (reinterpret_cast<uintptr_t>(p) % 8 == 0 && ld % 2 == 0); };
+  if (even(a.X, a.ldx) && (a.mode != 2 || even(a.Z, a.ldz))) k_to_frag<true><<<grid, 256, 0, st>>>(a);
+  else k_to_frag<false><<<grid, 256, 0, st>>>(a);
   HGNN_LAUNCH_CHECK("k_to_frag");
   return HGNN_OK;
 }
