@@ -41,6 +41,7 @@ struct FGemmArgs {
   long ld1 = 0;
   const float* r2 = nullptr;
   long ld2 = 0;
+  int vec = 1;                    // floats per access of Cf / r1 / r2 (set by the launcher from their alignment)
   // EPI_T and EPI_ROW: bias[group * bias_grp_stride + col] for col < nbias
   const float* bias = nullptr;
   int nbias = 0;

@@ -188,6 +188,73 @@ __global__ void __launch_bounds__(64 * NW, (WI * WJ <= 8 ? 2 : 1)) k_fgemm(FGemm
 
   // accumulator register v of lane (g, x): row 8 (v >> 2) + 4 g + (v & 3), column x of the 32 x 32 block
   const int g = lane >> 5, x = lane & 31;
+  if constexpr (EPI == EPI_ROW) {
+    // Row-major results go through the LDS, one 32-row block per wavefront row at a time (64 rows x 128 columns of
+    // fp32), so that bias, residuals and the output move as whole rows: a thread owns four consecutive columns.
+    static_assert(C::TJ == 4 && NW == 4 && C::LDS_BYTES >= 64 * 128 * 4, "staging tile is 64 rows x 128 columns");
+    float* stg = reinterpret_cast<float*>(lds);
+    const int c4 = (tid & 31) * 4, r8 = tid >> 5;
+    const int col = j0 * 32 + c4;
+    const bool col_ok = col < p.nJ * 32;
+    float bias4[4] = {0.f, 0.f, 0.f, 0.f};
+    if (p.bias) {
+#pragma unroll
+      for (int t = 0; t < 4; ++t)
+        if (col + t < p.nbias) bias4[t] = p.bias[(long)grp * p.bias_grp_stride + col + t];
+    }
+#pragma unroll
+    for (int i = 0; i < WI; ++i) {
+      __syncthreads();   // the fragments (or the previous block row) have been read
+#pragma unroll
+      for (int j = 0; j < WJ; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+          stg[(wi * 32 + 8 * (v >> 2) + 4 * g + (v & 3)) * 128 + wj * 64 + j * 32 + x] = acc[i][j][v];
+      __syncthreads();
+#pragma unroll
+      for (int rr = 0; rr < 8; ++rr) {
+        const int lrow = rr * 8 + r8;
+        const int prow = (i0 + (lrow >> 5) * WI + i) * 32 + (lrow & 31);
+        if (prow < mvalid && col_ok) {
+          const long row = p.row_idx ? p.row_idx[pos0 + prow - pad0] : prow;   // scatter to the caller's rows
+          const float4 sv = *reinterpret_cast<const float4*>(&stg[lrow * 128 + c4]);
+          float val[4] = {sv.x + bias4[0], sv.y + bias4[1], sv.z + bias4[2], sv.w + bias4[3]};
+          if (p.Cf && col < p.ncol_f) {
+            float* cp = p.Cf + row * p.ldc + col;
+            const float* p1 = p.r1 ? p.r1 + row * p.ld1 + col : nullptr;
+            const float* p2 = p.r2 ? p.r2 + row * p.ld2 + col : nullptr;
+            if (p.vec == 4 && col + 4 <= p.ncol_f) {
+              if (p1) { const float4 t = *reinterpret_cast<const float4*>(p1); val[0] += t.x; val[1] += t.y; val[2] += t.z; val[3] += t.w; }
+              if (p2) { const float4 t = *reinterpret_cast<const float4*>(p2); val[0] += t.x; val[1] += t.y; val[2] += t.z; val[3] += t.w; }
+              *reinterpret_cast<float4*>(cp) = make_float4(val[0], val[1], val[2], val[3]);
+            } else if (p.vec >= 2 && col + 4 <= p.ncol_f) {
+#pragma unroll
+              for (int h2 = 0; h2 < 2; ++h2) {
+                if (p1) { const float2 t = *reinterpret_cast<const float2*>(p1 + 2 * h2); val[2 * h2] += t.x; val[2 * h2 + 1] += t.y; }
+                if (p2) { const float2 t = *reinterpret_cast<const float2*>(p2 + 2 * h2); val[2 * h2] += t.x; val[2 * h2 + 1] += t.y; }
+                *reinterpret_cast<float2*>(cp + 2 * h2) = make_float2(val[2 * h2], val[2 * h2 + 1]);
+              }
+            } else {
+#pragma unroll
+              for (int t = 0; t < 4; ++t)
+                if (col + t < p.ncol_f) {
+                  if (p1) val[t] += p1[t];
+                  if (p2) val[t] += p2[t];
+                  cp[t] = val[t];
+                }
+            }
+          }
+          if (p.Cb) {   // all columns of the tile (the pitch is a multiple of 128)
+            uint2 w;
+            w.x = pack_bf16x2(val[0], val[1]);
+            w.y = pack_bf16x2(val[2], val[3]);
+            *reinterpret_cast<uint2*>(p.Cb + row * p.ldcb + col) = w;
+          }
+        }
+      }
+    }
+    return;
+  }
 #pragma unroll
   for (int j = 0; j < WJ; ++j) {
     const int jb = j0 + wj * WJ + j;
@@ -207,21 +274,6 @@ __global__ void __launch_bounds__(64 * NW, (WI * WJ <= 8 ? 2 : 1)) k_fgemm(FGemm
           w.z = pack_bf16x2(acc[i][j][8 * hh + 4] + bv, acc[i][j][8 * hh + 5] + bv);
           w.w = pack_bf16x2(acc[i][j][8 * hh + 6] + bv, acc[i][j][8 * hh + 7] + bv);
           *reinterpret_cast<uint4*>(p.T + ((long)(2 * ib + hh) * p.t_ncb + jb) * 1024 + lane * 16) = w;
-        }
-      } else if constexpr (EPI == EPI_ROW) {
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int prow = ib * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
-          if (prow < mvalid) {
-            const long row = p.row_idx ? p.row_idx[pos0 + prow - pad0] : prow;   // scatter to the caller's rows
-            float val = acc[i][j][v] + bv;
-            if (p.Cf && colx < p.ncol_f) {
-              if (p.r1) val += p.r1[row * p.ld1 + colx];
-              if (p.r2) val += p.r2[row * p.ld2 + colx];
-              p.Cf[row * p.ldc + colx] = val;
-            }
-            if (p.Cb) p.Cb[row * p.ldcb + colx] = (unsigned short)f2bf_bits(val);
-          }
         }
       } else {
         float* out = p.P + ((long)grp * p.nsplit + split) * p.split_stride;   // [group][split]
@@ -961,7 +1013,19 @@ int32_t launch_fwgrad(hipStream_t st, const FWgradArgs& a) {
   HGNN_LAUNCH_CHECK("k_reduce_wgrad");
   return HGNN_OK;
 }
-int32_t launch_fgemm_rows(hipStream_t st, const FGemmArgs& a) {
+// widest access (floats) that the fp32 output and the residuals of a row product allow
+static int row_io_width(const FGemmArgs& a) {
+  const auto fits = [&](int vec) {
+    const auto ok = [&](const float* p, long ld) {
+      return p == nullptr || (reinterpret_cast<uintptr_t>(p) % (4 * vec) == 0 && ld % vec == 0);
+    };
+    return ok(a.Cf, a.ldc) && ok(a.r1, a.ld1) && ok(a.r2, a.ld2);
+  };
+  return fits(4) ? 4 : (fits(2) ? 2 : 1);
+}
+int32_t launch_fgemm_rows(hipStream_t st, const FGemmArgs& a0) {
+  FGemmArgs a = a0;
+  a.vec = row_io_width(a);
   // few rows (atoms, graphs): 128 x 128 tiles give the launch enough workgroups to cover the chip
   const long big_tiles = (long)((a.nI + 7) / 8) * (a.nJ / 4) * (a.grp_ptr ? a.S : 1);
   if (big_tiles < 4L * num_cus()) return launch_fgemm_t<2, 2, EPI_ROW>(st, a);
