@@ -144,14 +144,15 @@ __global__ void __launch_bounds__(64 * NW, (WI * WJ <= 8 ? 2 : 1)) k_fgemm(FGemm
     }
     __syncthreads();
     // after the prologue: half 0 = step 0, Y = step 1, X = step 2
-    int slot = 0;
+    // (the number of steps is even, see the launcher: the loop body has no branch, which lets the compiler count the
+    // outstanding loads exactly instead of waiting for all of them)
     for (int c = 0; c < nch; c += 2) {
 #pragma unroll
       for (int par = 0; par < 2; ++par) {
         const int cc = c + par;
-        if (cc < nch) {   // uniform
-          const u32x4_t* cur = lds + slot * STAGE;
-          const int nslot = slot ^ 1;
+        {
+          const u32x4_t* cur = lds + par * STAGE;
+          const int nslot = par ^ 1;
 #pragma unroll
           for (int kk = 0; kk < C::KC; ++kk) {
             bf16x8_t a[WI], b[WJ];
@@ -180,7 +181,6 @@ __global__ void __launch_bounds__(64 * NW, (WI * WJ <= 8 ? 2 : 1)) k_fgemm(FGemm
             for (int s = 0; s < C::PASSES; ++s) preX[s] = *reinterpret_cast<const u32x4_t*>(src[s] + kn * kst[s]);
           }
           __syncthreads();
-          slot = nslot;
         }
       }
     }
@@ -290,8 +290,9 @@ __global__ void __launch_bounds__(64 * NW, (WI * WJ <= 8 ? 2 : 1)) k_fgemm(FGemm
 template <int WI, int WJ, int EPI, int NW = 4, int KC = 2>
 static int32_t launch_fgemm_t(hipStream_t st, const FGemmArgs& a) {
   using C = FCfg<WI, WJ, NW, KC>;
-  HGNN_REQUIRE(a.nI % C::TI == 0 && (a.nJ % C::TJ == 0 || EPI != EPI_PART) && a.nkb % C::KC == 0 &&
-                   a.kper % C::KC == 0 && a.kper > 0,
+  // (an even number of steps per workgroup: contraction counts are multiples of two steps)
+  HGNN_REQUIRE(a.nI % C::TI == 0 && (a.nJ % C::TJ == 0 || EPI != EPI_PART) && a.nkb % (2 * C::KC) == 0 &&
+                   a.kper % (2 * C::KC) == 0 && a.kper > 0,
                HGNN_ERR_BAD_SHAPE, "fragment GEMM: %d x %d blocks, %d contraction blocks do not tile", a.nI, a.nJ, a.nkb);
   if (a.nI == 0 || a.nJ == 0) return HGNN_OK;
   HGNN_REQUIRE(EPI == EPI_PART ? (a.nsplit % 8 == 0 && (long)a.nsplit * a.kper >= a.nkb) : (a.nsplit == 1 && a.kper == a.nkb),
@@ -996,8 +997,8 @@ int32_t launch_fwgrad(hipStream_t st, const FWgradArgs& a) {
   if (want < 8) want = 8;
   HGNN_REQUIRE(cap >= 8, HGNN_ERR_WORKSPACE_TOO_SMALL, "weight-gradient partials do not fit the workspace");
   int kper = (int)((g.nkb + want - 1) / want);
-  kper = (kper + 1) / 2 * 2;
-  if (kper < 2) kper = 2;
+  kper = (kper + 3) / 4 * 4;   // whole pairs of steps
+  if (kper < 4) kper = 4;
   g.kper = kper;
   g.nsplit = (int)want;   // splits past the end of the rows write zeros
   g.P = a.partial; g.ldp = (long)a.nJ * 32; g.split_stride = (long)a.nI * 32 * a.nJ * 32;
