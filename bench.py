@@ -49,7 +49,7 @@ def kernel_work(tag, N, E, H, dtype):
         return 2.0 * NH * H, 2 * NH * 4
     if tag == "colsum":
         return 0.0, NH * 4
-    # widths above 256 (fragment-GEMM path, bf16): per-edge products run as plain GEMMs over materialised tensors
+    # widths other than 64 / 128 / 256 (fragment-GEMM path, bf16): per-edge products run as plain GEMMs over materialised tensors
     if tag == "frag_gemm_edge":      # in: a1 (or g_z2) + W2; out: z2 (or g_a1)
         return 2.0 * EH * H, 2 * EH * b + 2.0 * H * H
     if tag == "frag_wgrad_edge":     # in: a1, g_z2; out: H x H

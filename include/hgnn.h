@@ -122,8 +122,8 @@ int32_t hgnn_embed_bwd(void* stream, int32_t N, int32_t H, const int32_t* Z,
  * _bwd takes g_h_out = dL/dh', g_v_out = dL/dv' and writes g_h_in = dL/dh, g_v_in = dL/dv and gW.
  * d2 and rvec are constants of the step (no gradient with respect to positions).
  * h_out may not alias h_in; g_h_in may not alias g_h_out.
- * H is 64, 128 or 256 (either dtype), or any width in 257..1024 with dtype HGNN_BF16 (the paper's backbone has 866
- * hidden units, section "Numerical Results"; such widths are padded to a multiple of 128 inside the library and
+ * H is 64, 128 or 256 (either dtype), or any other width in 1..1024 with dtype HGNN_BF16 (the paper's backbone has
+ * 866 hidden units, section "Numerical Results"; such widths are padded to a multiple of 128 inside the library and
  * float32 operands are UNIMPLEMENTED for them).
  * Errors: BAD_SHAPE for any other H or an unknown dtype; OVERFLOW if E > 2^31 - 129 or
  * N * 2H * 4 bytes reaches 4 GiB (the edge kernels index edges and gathered rows with 32 bits);

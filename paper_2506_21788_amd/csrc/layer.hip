@@ -128,9 +128,9 @@ static int32_t check_layer_args(int N, int64_t E, int H, int dtype) {
   HGNN_REQUIRE((int64_t)N * 2 * H * 4 < (1ll << 32), HGNN_ERR_OVERFLOW,
                "N * 2H * 4 bytes must stay below 4 GiB (N = %d, H = %d)", N, H);
   HGNN_REQUIRE(dtype == HGNN_F32 || dtype == HGNN_BF16, HGNN_ERR_BAD_SHAPE, "unknown dtype %d", dtype);
-  HGNN_REQUIRE(valid_H(H) || wide_H(H), HGNN_ERR_BAD_SHAPE, "H must be 64, 128, 256 or lie in 257..1024 (got %d)", H);
+  HGNN_REQUIRE(valid_H(H) || wide_H(H), HGNN_ERR_BAD_SHAPE, "H must lie in 1..1024 (got %d)", H);
   HGNN_REQUIRE(!wide_H(H) || dtype == HGNN_BF16, HGNN_ERR_UNIMPLEMENTED,
-               "widths above 256 run with bf16 operands only (H = %d)", H);
+               "widths other than 64, 128, 256 run with bf16 operands only (H = %d)", H);
   return HGNN_OK;
 }
 

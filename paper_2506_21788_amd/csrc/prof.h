@@ -29,10 +29,10 @@ enum ProfTag : int {
   PT_MISC,
   PT_EDGE_FUSED_FWD,    // fused gather + GEMM + segmented reduction (forward)
   PT_EDGE_FUSED_BWD,    // fused backward edge kernels
-  PT_FRAG_GEMM_EDGE,    // widths above 256: per-edge H x H products (z2 = a1 W2, g_a1 = g_z2 W2^T)
-  PT_FRAG_WGRAD_EDGE,   // widths above 256: g_W2 = a1^T g_z2 (+ its partial reduction)
-  PT_EDGE_ELEM,         // widths above 256: element-wise edge kernels (a1, g_z2, g_z1)
-  PT_TO_FRAG,           // widths above 256: row-major -> fragment conversions of atom tensors
+  PT_FRAG_GEMM_EDGE,    // fragment path (widths other than 64 / 128 / 256): per-edge H x H products (z2 = a1 W2, g_a1 = g_z2 W2^T)
+  PT_FRAG_WGRAD_EDGE,   // fragment path (widths other than 64 / 128 / 256): g_W2 = a1^T g_z2 (+ its partial reduction)
+  PT_EDGE_ELEM,         // fragment path (widths other than 64 / 128 / 256): element-wise edge kernels (a1, g_z2, g_z1)
+  PT_TO_FRAG,           // fragment path (widths other than 64 / 128 / 256): row-major -> fragment conversions of atom tensors
   PT_COUNT
 };
 

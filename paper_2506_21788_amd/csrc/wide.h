@@ -1,6 +1,7 @@
-// Message-passing layer for hidden widths above 256 (the paper's backbone has 866 hidden units, section
-// "Numerical Results"): at such widths the per-edge H x H product dominates and is bound by the matrix cores,
-// so the edge tensors are materialised and every product runs through one fragment GEMM kernel (internal).
+// Message-passing layer for hidden widths other than 64 / 128 / 256, up to 1024 (the paper's backbone has 866 hidden
+// units, section "Numerical Results"): at large widths the per-edge H x H product dominates and is bound by the
+// matrix cores, so the edge tensors are materialised and every product runs through one fragment GEMM kernel
+// (internal). Small odd widths take the same path for generality, padded to 128.
 //
 // All matrix operands live in HBM as 1 KiB "fragments" = what one wavefront feeds to one
 // v_mfma_f32_32x32x16_bf16 (64 lanes x 8 bf16), so that staging and operand loads are straight copies:
@@ -17,7 +18,8 @@
 
 namespace hgnn {
 
-inline bool wide_H(int H) { return H > 256 && H <= 1024; }
+// every width from 1 to 1024 that the fused narrow kernels (64, 128, 256) do not serve
+inline bool wide_H(int H) { return H >= 1 && H <= 1024 && H != 64 && H != 128 && H != 256; }
 inline int wide_pad_cols(int H) { return (H + 127) / 128 * 128; }
 inline int64_t wide_pad_rows(int64_t M) { return (M + 255) / 256 * 256; }
 

@@ -1,4 +1,4 @@
-// Message-passing layer for hidden widths above 256 (see wide.h for the operand layouts):
+// Message-passing layer for hidden widths other than 64 / 128 / 256 (see wide.h for the operand layouts):
 //   k_fgemm        one kernel for every product: out[i][j] += A(i, kb) x B(j, kb) over 1 KiB fragments staged through
 //                  LDS; epilogues: result as T fragments (edge tensors), row-major fp32 / bf16 with bias and
 //                  residuals (atom tensors), fp32 split partials (weight gradients)
@@ -838,6 +838,8 @@ static int32_t launch_seg_fwd_w(hipStream_t st, int Hp, int N, const int32_t* ro
   ProfScope ps(PT_SEG_FWD, st);
   const unsigned grid = (unsigned)((N + 3) / 4);
   switch (Hp / 32) {
+    case 4: k_seg_fwd_w<4><<<grid, 256, 0, st>>>(N, row_ptr, z2_T, rvec, wx, H, alpha, v_in, M, v_out); break;
+    case 8: k_seg_fwd_w<8><<<grid, 256, 0, st>>>(N, row_ptr, z2_T, rvec, wx, H, alpha, v_in, M, v_out); break;
     case 12: k_seg_fwd_w<12><<<grid, 256, 0, st>>>(N, row_ptr, z2_T, rvec, wx, H, alpha, v_in, M, v_out); break;
     case 16: k_seg_fwd_w<16><<<grid, 256, 0, st>>>(N, row_ptr, z2_T, rvec, wx, H, alpha, v_in, M, v_out); break;
     case 20: k_seg_fwd_w<20><<<grid, 256, 0, st>>>(N, row_ptr, z2_T, rvec, wx, H, alpha, v_in, M, v_out); break;

@@ -104,9 +104,10 @@ def test_deep_heads_and_wide_layer_error_paths():
     B.multihead_deep_fwd(N, G, H, Hh, D, S, B.BF16, plan, p, h, v, Wh, e, f, sv, ws)   # the good call still works
     torch.cuda.synchronize()
     assert bool(torch.isfinite(e).all())
-    # the layer above H = 256: float32 operands are not implemented, small buffers are refused
+    # the layer at other widths than 64, 128, 256: float32 operands are not implemented, small buffers are refused
     assert code(lambda: B.mp_layer_workspace_bytes(N, 50, 300, B.F32)) == -9
     assert code(lambda: B.mp_layer_workspace_bytes(N, 50, 1025, B.BF16)) == -2
+    assert code(lambda: B.mp_layer_workspace_bytes(N, 50, 0, B.BF16)) == -2
     lws, lsv = B.mp_layer_workspace_bytes(N, 0, 300, B.BF16)
     W = torch.zeros(6 * 300 * 300 + 6 * 300, **f32)
     row_ptr = torch.zeros(N + 1, dtype=torch.int32, device="cuda")

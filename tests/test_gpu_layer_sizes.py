@@ -75,9 +75,10 @@ def test_layer_other_modes_edge_counts(H, dtype, E):
     _run_layer(N=300, E=E, H=H, dtype=dtype, seed=E)
 
 
-# Widths above 256 take the fragment-GEMM path (bf16 operands, width padded to a multiple of 128, rows to 256):
-# the paper's 866, widths on both sides of the padding steps, edge counts around the 16 / 32 / 256-row groups.
+# Widths other than 64 / 128 / 256 take the fragment-GEMM path (bf16 operands, width padded to a multiple of 128, rows
+# to 256): the paper's 866, widths on both sides of the padding steps, odd and small widths, edge counts around the
+# 16 / 32 / 256-row groups.
 @pytest.mark.parametrize("H,N,E", [(866, 300, 5000), (384, 200, 3001), (1024, 257, 777), (866, 40, 0), (320, 513, 9000),
-                                   (500, 64, 256), (866, 5, 17)])
+                                   (500, 64, 256), (866, 5, 17), (333, 100, 1500), (257, 33, 700), (100, 80, 900), (24, 50, 300)])
 def test_layer_wide_widths(H, N, E):
     _run_layer(N=N, E=E, H=H, dtype="bf16", seed=H + E)
