@@ -176,6 +176,8 @@ int32_t hgnn_pool_by_graph_bwd(void* stream, int32_t N, int32_t G, int32_t H, in
  *   q_i = Wf2_s . silu(Wf1_s^T h_i + bf1_s) + bf2_s ,  F_i = q_i * v_i     (atomic force)
  * Whead: S branches back to back, each  We1[H,Hh] be1[Hh] We2[Hh] be2[1] Wf1[H,Hh] bf1[Hh] Wf2[Hh]
  * bf2[1]. gWhead has the same layout; a branch with no graph in the batch gets exactly zero.
+ * H in {64, 128, 256} with Hh = H runs with either dtype; any other H, Hh in 1..1024 is the D = 1 case of
+ * hgnn_multihead_deep_* below (HGNN_BF16 only).
  *
  * hgnn_multihead_plan groups graphs and their atoms by source (stable): plan is an int32 array of
  * hgnn_multihead_plan_ints(N,G,S) entries laid out as

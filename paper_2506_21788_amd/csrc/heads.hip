@@ -432,6 +432,10 @@ static int32_t check_head_args(int N, int G, int H, int Hh, int S, int dtype) {
 
 using namespace hgnn;
 
+// plain heads at a width the block kernels do not serve (H outside {64, 128, 256} or Hh != H): the same computation
+// is the one-hidden-layer case of the deep heads (same buffer layout)
+static bool heads_need_fragment_path(int H, int Hh) { return !valid_H(H) || Hh != H; }
+
 extern "C" int32_t hgnn_embed_fwd(void* stream, int32_t N, int32_t H, const int32_t* Z, const float* emb, float* h) {
   hipStream_t st = static_cast<hipStream_t>(stream);
   HGNN_REQUIRE(N >= 0 && any_H(H), HGNN_ERR_BAD_SHAPE, "embed_fwd: bad N or H");
@@ -528,6 +532,8 @@ extern "C" int32_t hgnn_multihead_plan(void* stream, int32_t N, int32_t G, int32
 extern "C" int32_t hgnn_multihead_decode_workspace_bytes(int32_t N, int32_t G, int32_t H, int32_t Hh, int32_t S,
                                                          int32_t dtype, size_t* ws_bytes_host,
                                                          size_t* saved_bytes_host) {
+  if (heads_need_fragment_path(H, Hh))
+    return hgnn_multihead_deep_workspace_bytes(N, G, H, Hh, 1, S, dtype, ws_bytes_host, saved_bytes_host);
   HGNN_TRY(check_head_args(N, G, H, Hh, S, dtype));
   HGNN_REQUIRE(ws_bytes_host && saved_bytes_host, HGNN_ERR_NULLPTR, "null size pointer");
   *ws_bytes_host = carve_head_ws(nullptr, N, G, H, Hh, S, dtype == HGNN_BF16).bytes;
@@ -540,6 +546,9 @@ extern "C" int32_t hgnn_multihead_decode_fwd(void* stream, int32_t N, int32_t G,
                                              const float* v, const float* Whead, float* energy, float* force,
                                              void* saved, size_t saved_bytes, void* ws, size_t ws_bytes) {
   hipStream_t st = static_cast<hipStream_t>(stream);
+  if (heads_need_fragment_path(H, Hh))
+    return hgnn_multihead_deep_fwd(stream, N, G, H, Hh, 1, S, dtype, plan, p, h, v, Whead, energy, force, saved,
+                                   saved_bytes, ws, ws_bytes);
   HGNN_TRY(check_head_args(N, G, H, Hh, S, dtype));
   if (G == 0 && N == 0) return HGNN_OK;
   HGNN_REQUIRE(plan && Whead && saved && ws, HGNN_ERR_NULLPTR, "multihead_decode_fwd: null pointer");
@@ -593,6 +602,9 @@ extern "C" int32_t hgnn_multihead_decode_bwd(void* stream, int32_t N, int32_t G,
                                              float* g_p, float* g_h, float* g_v, float* gWhead, void* ws,
                                              size_t ws_bytes) {
   hipStream_t st = static_cast<hipStream_t>(stream);
+  if (heads_need_fragment_path(H, Hh))
+    return hgnn_multihead_deep_bwd(stream, N, G, H, Hh, 1, S, dtype, plan, p, h, v, Whead, saved, saved_bytes, g_energy,
+                                   g_force, g_p, g_h, g_v, gWhead, ws, ws_bytes);
   HGNN_TRY(check_head_args(N, G, H, Hh, S, dtype));
   HGNN_REQUIRE(gWhead && Whead && ws, HGNN_ERR_NULLPTR, "multihead_decode_bwd: null pointer");
   const HeadOff o(H, Hh);

@@ -88,10 +88,10 @@ def test_host_side_argument_checks_need_no_gpu():
     assert lib.hgnn_mp_layer_workspace_bytes(ctypes.c_int32(1000), ctypes.c_int64(32000), ctypes.c_int32(256),
                                              ctypes.c_int32(0), ctypes.byref(a), ctypes.byref(s32)) == 0
     assert s16.value < 32000 * 256 * 2 * 2 <= s32.value
-    # head width must equal H
-    rc = lib.hgnn_multihead_decode_workspace_bytes(ctypes.c_int32(10), ctypes.c_int32(2), ctypes.c_int32(128),
-                                                   ctypes.c_int32(64), ctypes.c_int32(2), ctypes.c_int32(0),
-                                                   ctypes.byref(a), ctypes.byref(s))
-    assert rc == -2
+    # a head width other than H is served by the one-hidden-layer case of the deep heads: bf16 operands only
+    hw = lambda Hh, dt: lib.hgnn_multihead_decode_workspace_bytes(
+        ctypes.c_int32(10), ctypes.c_int32(2), ctypes.c_int32(128), ctypes.c_int32(Hh), ctypes.c_int32(2),
+        ctypes.c_int32(dt), ctypes.byref(a), ctypes.byref(s))
+    assert hw(64, 0) == code and hw(64, 1) == 0 and hw(2000, 1) == -2 and hw(128, 0) == 0
     lib.hgnn_multihead_plan_ints.restype = ctypes.c_int64
     assert lib.hgnn_multihead_plan_ints(ctypes.c_int32(7), ctypes.c_int32(3), ctypes.c_int32(2)) >= 2 * 3 + 7 + 3 + 3

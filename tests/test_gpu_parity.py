@@ -432,6 +432,18 @@ def test_step_small_mixed_paper_shape():
     compare_step(_paper_shape_small(), "small H=866 Hh=889 D=3 bf16")
 
 
+def test_step_odd_width_plain_heads():
+    """H = 100 with the plain heads of width 72: the layer takes the fragment path, the plain-heads entry points are
+    served by the deep heads with one hidden layer."""
+    say("step small mixed, H = 100, plain heads of width 72")
+    from hgnn_inputs import init_head_weights
+    b = small_mixed_batch(12, n_mol=4, n_cry=3, S=2, mol_atoms=(3, 30), cry_atoms=(2, 20))
+    P = problem_from_batch(b, 4.5, 100, 2, 2, "bf16", seed=100)
+    P["Wh"] = init_head_weights(np.random.default_rng(5), 100, 72, 2)
+    P["hp"]["Hh"] = 72
+    compare_step(P, "small H=100 Hh=72 bf16")
+
+
 def test_full_size_cfg6_sampled_graphs():
     """Config 6 (128 structures, ~8k atoms, ~250k edges, H = 866, 4 layers, heads 3 x 889). A graph's outputs depend
     on that graph only, so the oracle recomputes sampled graphs as a batch of their own."""
