@@ -68,6 +68,7 @@ def _run(G, atoms, H, Hh, D, S, seed, sources=None):
     (12, (2, 40), 256, 300, 2, 2, None),
     (9, (1, 12), 130, 70, 4, 4, (0, 2)),      # two sources absent from the batch
     (700, (1, 2), 96, 128, 2, 2, None),       # more than 256 graphs per source: several row tiles per group
+    (15, (0, 4), 200, 150, 3, 3, None),       # graphs without atoms (their energy is the head of a zero vector)
 ])
 def test_deep_heads_match_the_oracle(G, atoms, H, Hh, D, S, sources):
     _run(G, atoms, H, Hh, D, S, seed=G + H + D, sources=sources)
