@@ -2,6 +2,7 @@
 
 Layout of one message-passing layer (float32, matrices row-major [in, out]):
     W1[(2H+1), H]  rows 0..H-1 act on h_i (destination), H..2H-1 on h_j (source), row 2H on d^2
+                   (with k edge attributes in place of d^2: W1[(2H+k), H], rows 2H..2H+k-1 on the attributes)
     b1[H]  W2[H,H]  b2[H]  wx[H]  W3[2H,H] (rows 0..H-1 on h_i, H..2H-1 on M_i)  b3[H]  W4[H,H]  b4[H]
 Layout of one source's decoding branch:
     We1[H,Hh] be1[Hh] We2[Hh] be2[1]   (energy head)   Wf1[H,Hh] bf1[Hh] Wf2[Hh] bf2[1]   (force head)
@@ -19,8 +20,8 @@ LAYER_FIELDS = ("W1", "b1", "W2", "b2", "wx", "W3", "b3", "W4", "b4")
 HEAD_FIELDS = ("We1", "be1", "We2", "be2", "Wf1", "bf1", "Wf2", "bf2")
 
 
-def _layer_shapes(H):
-    return {"W1": (2 * H + 1, H), "b1": (H,), "W2": (H, H), "b2": (H,), "wx": (H,),
+def _layer_shapes(H, k=1):
+    return {"W1": (2 * H + k, H), "b1": (H,), "W2": (H, H), "b2": (H,), "wx": (H,),
             "W3": (2 * H, H), "b3": (H,), "W4": (H, H), "b4": (H,)}
 
 
@@ -38,16 +39,16 @@ def _slices(shapes, order):
     return out, o
 
 
-def layer_field_slices(H):
-    return _slices(_layer_shapes(H), LAYER_FIELDS)[0]
+def layer_field_slices(H, k=1):
+    return _slices(_layer_shapes(H, k), LAYER_FIELDS)[0]
 
 
 def head_field_slices(H, Hh):
     return _slices(_head_shapes(H, Hh), HEAD_FIELDS)[0]
 
 
-def layer_weight_count(H):
-    return _slices(_layer_shapes(H), LAYER_FIELDS)[1]
+def layer_weight_count(H, k=1):
+    return _slices(_layer_shapes(H, k), LAYER_FIELDS)[1]
 
 
 def head_weight_count(H, Hh):
@@ -66,10 +67,11 @@ def _fill(rng, shapes, order, fan_in, bias_scale):
     return np.concatenate(parts).astype(np.float32)
 
 
-def init_layer_weights(rng, H, bias_scale=0.1):
-    """U(-1/sqrt(fan_in), 1/sqrt(fan_in)) matrices; small non-zero biases so a dropped bias shows."""
-    fan = {"W1": 2 * H + 1, "W2": H, "wx": H, "W3": 2 * H, "W4": H}
-    return _fill(rng, _layer_shapes(H), LAYER_FIELDS, fan, bias_scale)
+def init_layer_weights(rng, H, bias_scale=0.1, k=1):
+    """U(-1/sqrt(fan_in), 1/sqrt(fan_in)) matrices; small non-zero biases so a dropped bias shows.
+    k: edge attributes (W1 has 2H + k rows)."""
+    fan = {"W1": 2 * H + k, "W2": H, "wx": H, "W3": 2 * H, "W4": H}
+    return _fill(rng, _layer_shapes(H, k), LAYER_FIELDS, fan, bias_scale)
 
 
 def init_head_weights(rng, H, Hh, S, bias_scale=0.1):

@@ -24,6 +24,7 @@ from .model import (  # noqa: F401
     dsilu,
     embed_fwd,
     embed_bwd,
+    edge_rbf,
     mp_layer_fwd,
     mp_layer_bwd,
     pool_fwd,

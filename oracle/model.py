@@ -30,9 +30,10 @@ _LAYER_FIELDS = ("W1", "b1", "W2", "b2", "wx", "W3", "b3", "W4", "b4")
 _HEAD_FIELDS = ("We1", "be1", "We2", "be2", "Wf1", "bf1", "Wf2", "bf2")
 
 
-def unpack_layer(flat, H):
-    """Views into one layer's flat buffer, in the documented field order (matrices are [in, out])."""
-    shapes = {"W1": (2 * H + 1, H), "b1": (H,), "W2": (H, H), "b2": (H,), "wx": (H,),
+def unpack_layer(flat, H, k=1):
+    """Views into one layer's flat buffer, in the documented field order (matrices are [in, out]).
+    k: number of edge attributes (rows 2H .. 2H+k-1 of W1 act on them; k = 1: the squared distance)."""
+    shapes = {"W1": (2 * H + k, H), "b1": (H,), "W2": (H, H), "b2": (H,), "wx": (H,),
               "W3": (2 * H, H), "b3": (H,), "W4": (H, H), "b4": (H,)}
     out, o = {}, 0
     for k in _LAYER_FIELDS:
@@ -87,18 +88,36 @@ def embed_bwd(Z, g_h, n_rows):
 
 
 # ---------------------------------------------------------------------------------------------
+# radial basis of the edge length (the "k" edge attributes of an edge input [h_i ; h_j ; attr] of width 2H + k)
+# ---------------------------------------------------------------------------------------------
+def edge_rbf(d2, k, rc):
+    """attr[e, j] = exp(-gamma (d_e - mu_j)^2) * fc(d_e),  d = sqrt(d2),  mu_j = j rc / (k - 1),
+    gamma = ((k - 1) / rc)^2 (neighbouring Gaussians cross at exp(-1/4)),  fc(d) = (cos(pi d / rc) + 1) / 2
+    (smooth cutoff: every attribute vanishes at d = rc).  k >= 2.  The paper names no basis: this is the usual
+    Gaussian expansion of interatomic distances."""
+    assert k >= 2
+    d = np.sqrt(np.asarray(d2, dtype=np.float64))
+    mu = np.arange(k, dtype=np.float64) * (rc / (k - 1))
+    gamma = ((k - 1) / rc) ** 2
+    fc = 0.5 * (np.cos(np.pi * d / rc) + 1.0)
+    return np.exp(-gamma * (d[:, None] - mu[None, :]) ** 2) * fc[:, None]
+
+
+# ---------------------------------------------------------------------------------------------
 # message-passing layer
 # ---------------------------------------------------------------------------------------------
-def mp_layer_fwd(h, v, dst, col, d2, rvec, Wflat, alpha):
+def mp_layer_fwd(h, v, dst, col, d2, rvec, Wflat, alpha, attr=None):
     """One layer. h [N,H], v [N,3]; dst/col [E] destination/source atom of each edge; d2 [E];
-    rvec [E,3]. Returns (h', v', cache-for-backward)."""
+    rvec [E,3]; attr [E,k] (optional): edge attributes that take the place of d2 in the edge input,
+    W1 then has 2H + k rows. Returns (h', v', cache-for-backward)."""
     h = np.asarray(h, dtype=np.float64)
     v = np.asarray(v, dtype=np.float64)
     N, H = h.shape
-    W = {k: np.asarray(a, dtype=np.float64) for k, a in unpack_layer(Wflat, H).items()}
     d2 = np.asarray(d2, dtype=np.float64)
+    eattr = d2[:, None] if attr is None else np.asarray(attr, dtype=np.float64)
+    W = {k: np.asarray(a, dtype=np.float64) for k, a in unpack_layer(Wflat, H, eattr.shape[1]).items()}
     rvec = np.asarray(rvec, dtype=np.float64)
-    xin = np.concatenate([h[dst], h[col], d2[:, None]], axis=1)          # [E, 2H+1]
+    xin = np.concatenate([h[dst], h[col], eattr], axis=1)                # [E, 2H+k]
     z1 = xin @ W["W1"] + W["b1"]
     a1 = silu(z1)
     z2 = a1 @ W["W2"] + W["b2"]
@@ -377,10 +396,10 @@ def heads_deep_bwd(cache, g_energy, g_force):
 # whole step
 # ---------------------------------------------------------------------------------------------
 def step_fwd_bwd(Z, graph_off, source_id, graph, emb, layer_weights, head_weights, Hh, S, alpha,
-                 g_energy=None, g_force=None, keep_layers=False, D=None):
+                 g_energy=None, g_force=None, keep_layers=False, D=None, attr=None):
     """Embedding -> L layers -> mean pool -> heads, then (if upstream gradients are given) the
     whole reverse pass. `graph` is the dict returned by oracle.radius_graph. D: hidden layers per
-    head (None: the one-hidden-layer heads of heads_fwd)."""
+    head (None: the one-hidden-layer heads of heads_fwd). attr [E,k]: edge attributes in place of d2."""
     H = emb.shape[1]
     N = len(Z)
     dst, col, d2, rvec = graph["dst"], graph["col"], graph["d2"], graph["rvec"]
@@ -388,7 +407,7 @@ def step_fwd_bwd(Z, graph_off, source_id, graph, emb, layer_weights, head_weight
     v = np.zeros((N, 3), dtype=np.float64)
     caches, hs = [], [h]
     for Wl in layer_weights:
-        h, v, c = mp_layer_fwd(h, v, dst, col, d2, rvec, Wl, alpha)
+        h, v, c = mp_layer_fwd(h, v, dst, col, d2, rvec, Wl, alpha, attr=attr)
         caches.append(c)
         if keep_layers:
             hs.append(h)

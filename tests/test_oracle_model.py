@@ -6,7 +6,7 @@ import pytest
 import torch
 
 import oracle
-from hgnn_inputs import (concat_graphs, head_field_slices, head_weight_count, init_embedding,
+from hgnn_inputs import (LAYER_FIELDS, concat_graphs, head_field_slices, head_weight_count, init_embedding,
                          init_head_weights, init_layer_weights, layer_field_slices,
                          layer_weight_count, small_mixed_batch, upstream_grads)
 from hgnn_inputs.structures import Batch
@@ -612,3 +612,89 @@ def test_whole_step_with_deep_heads_by_finite_differences():
 
     num = (loss(+1) - loss(-1)) / (2 * eps)
     assert abs(num - ana) <= 1e-6 * max(1.0, abs(ana)), (num, ana)
+
+
+# ---------------------------------------------------------------------------------------------
+# k edge attributes (radial basis of the edge length) in place of d^2
+# ---------------------------------------------------------------------------------------------
+def test_edge_rbf_closed_forms():
+    k, rc = 7, 5.0
+    mu = [j * rc / (k - 1) for j in range(k)]
+    fc = lambda d: 0.5 * (math.cos(math.pi * d / rc) + 1.0)
+    # at a centre the Gaussian is 1: only the cutoff envelope remains; at d = 0 that is 1, at d = rc it is 0
+    a = oracle.edge_rbf(np.array([m * m for m in mu]), k, rc)
+    for j in range(k):
+        assert abs(a[j, j] - fc(mu[j])) <= 1e-15
+    assert a[0, 0] == 1.0 and np.all(np.abs(a[-1]) <= 1e-30)
+    # half way between two centres both Gaussians are exp(-1/4)
+    mid = 0.5 * (mu[2] + mu[3])
+    b = oracle.edge_rbf(np.array([mid * mid]), k, rc)[0]
+    assert abs(b[2] - math.exp(-0.25) * fc(mid)) <= 1e-15 and abs(b[2] - b[3]) <= 1e-15
+    # value by value with scalar arithmetic
+    rng = np.random.default_rng(0)
+    d = rng.uniform(0.0, rc, size=50)
+    got = oracle.edge_rbf(d * d, k, rc)
+    for e in range(50):
+        for j in range(k):
+            want = math.exp(-((k - 1) / rc) ** 2 * (d[e] - mu[j]) ** 2) * fc(d[e])
+            assert abs(got[e, j] - want) <= 1e-14
+    # smooth at the cutoff: the slope of every attribute vanishes there
+    h = 1e-6
+    lo = oracle.edge_rbf(np.array([(rc - h) ** 2]), k, rc)[0]
+    assert np.all(np.abs(lo) <= 1e-10)
+
+
+def test_layer_with_one_attribute_equal_to_d2_is_the_plain_layer():
+    P = make_problem(seed=40, H=6, L=1)
+    g, b = P["g"], P["b"]
+    rng = np.random.default_rng(3)
+    h = rng.standard_normal((b.N, P["H"]))
+    v = rng.standard_normal((b.N, 3))
+    a = oracle.mp_layer_fwd(h, v, g["dst"], g["col"], g["d2"], g["rvec"], P["Ws"][0], P["alpha"])
+    c = oracle.mp_layer_fwd(h, v, g["dst"], g["col"], g["d2"], g["rvec"], P["Ws"][0], P["alpha"],
+                            attr=np.asarray(g["d2"], dtype=np.float64)[:, None])
+    assert np.array_equal(a[0], c[0]) and np.array_equal(a[1], c[1])
+
+
+def test_layer_with_k_attributes_backward_equals_torch_autograd_and_finite_differences():
+    P = make_problem(seed=41, H=5, L=1)
+    g, b, H, k = P["g"], P["b"], P["H"], 4
+    rng = np.random.default_rng(4)
+    W = init_layer_weights(rng, H, k=k).astype(np.float64)
+    assert len(W) == layer_weight_count(H, k) == (2 * H + k) * H + 5 * H + 3 * H * H + H * H
+    h = rng.standard_normal((b.N, H))
+    v = rng.standard_normal((b.N, 3))
+    attr = oracle.edge_rbf(g["d2"], k, P["rc"])
+    gh = rng.standard_normal((b.N, H))
+    gv = rng.standard_normal((b.N, 3))
+    ho, vo, cache = oracle.mp_layer_fwd(h, v, g["dst"], g["col"], g["d2"], g["rvec"], W, P["alpha"], attr=attr)
+    g_h, g_v, gW = oracle.mp_layer_bwd(cache, gh, gv)
+    # torch: the forward written with torch ops on the flat buffer
+    sl = layer_field_slices(H, k)
+    tW, th, tv = torch.tensor(W, requires_grad=True), torch.tensor(h, requires_grad=True), torch.tensor(v, requires_grad=True)
+    f = {n: tW[lo:hi].reshape(shp) for n, (lo, hi, shp) in sl.items()}
+    dst = torch.as_tensor(g["dst"], dtype=torch.long)
+    col = torch.as_tensor(g["col"], dtype=torch.long)
+    silu = torch.nn.functional.silu
+    m = silu(silu(torch.cat([th[dst], th[col], torch.as_tensor(attr)], 1) @ f["W1"] + f["b1"]) @ f["W2"] + f["b2"])
+    M = torch.zeros(b.N, H, dtype=torch.float64).index_add(0, dst, m) * P["alpha"]
+    v2 = tv + P["alpha"] * torch.zeros(b.N, 3, dtype=torch.float64).index_add(
+        0, dst, (m @ f["wx"])[:, None] * torch.as_tensor(g["rvec"], dtype=torch.float64))
+    h2 = th + silu(torch.cat([th, M], 1) @ f["W3"] + f["b3"]) @ f["W4"] + f["b4"]
+    assert np.allclose(h2.detach().numpy(), ho, rtol=1e-12, atol=1e-12)
+    (torch.sum(h2 * torch.as_tensor(gh)) + torch.sum(v2 * torch.as_tensor(gv))).backward()
+    flat = np.concatenate([np.ravel(gW[n]) for n in LAYER_FIELDS])
+    for mine, ref in ((flat, tW.grad.numpy()), (g_h, th.grad.numpy()), (g_v, tv.grad.numpy())):
+        assert np.max(np.abs(mine - ref)) <= 1e-10 * max(1.0, np.max(np.abs(ref)))
+    # finite differences on the rows of W1 that act on the attributes
+    lo = sl["W1"][0] + 2 * H * H
+    d = np.zeros_like(W)
+    d[lo:lo + k * H] = rng.standard_normal(k * H)
+    eps = 1e-6
+
+    def loss(Wx):
+        a, c, _ = oracle.mp_layer_fwd(h, v, g["dst"], g["col"], g["d2"], g["rvec"], Wx, P["alpha"], attr=attr)
+        return float(np.sum(a * gh) + np.sum(c * gv))
+
+    num = (loss(W + eps * d) - loss(W - eps * d)) / (2 * eps)
+    assert abs(num - np.sum(flat * d)) <= 1e-6 * max(1.0, abs(num))
