@@ -157,6 +157,39 @@ int32_t hgnn_mp_layer_bwd(void* stream, int32_t N, int64_t E, int32_t H, int32_t
                           float* gW /*out, layout of W*/, void* ws, size_t ws_bytes);
 
 /* ---------------------------------------------------------------------------------------------
+ * The same layer with k edge attributes in place of d2: the edge input is [h_i ; h_j ; attr_e] of width 2H + k
+ * and W1 has 2H + k rows (rows 2H .. 2H+k-1 act on the attributes; everything after W1 in W and gW moves
+ * accordingly: (6H^2 + (5 + k) H floats). attr is [E,k] float32, a constant of the step like d2.
+ * hgnn_edge_rbf fills it with a radial basis of the edge length d = sqrt(d2) (the paper names no basis; this is the
+ * usual Gaussian expansion with a smooth cutoff):
+ *   attr[e][j] = exp(-gamma (d - mu_j)^2) * (cos(pi d / rc) + 1) / 2,  mu_j = j rc / (k-1),  gamma = ((k-1) / rc)^2
+ * 2 <= k <= 16 there; the layer takes 1 <= k <= 16 and any attributes. 1 <= H <= 1024, dtype HGNN_BF16 only (HGNN_F32
+ * -> UNIMPLEMENTED): at every width this variant runs through the fragment-GEMM kernels. Other arguments, side
+ * stream, errors and aliasing rules as for hgnn_mp_layer_*. Only enqueue work.
+ * ------------------------------------------------------------------------------------------- */
+int32_t hgnn_edge_rbf(void* stream, int64_t E, const float* d2 /*[E]*/, int32_t k, float rc,
+                      float* attr /*out [E,k]*/);
+
+int32_t hgnn_mp_layer_attr_workspace_bytes(int32_t N, int64_t E, int32_t H, int32_t k, int32_t dtype,
+                                           size_t* ws_bytes_host, size_t* saved_bytes_host);
+
+int32_t hgnn_mp_layer_attr_fwd(void* stream, int32_t N, int64_t E, int32_t H, int32_t k, int32_t dtype, float alpha,
+                               const int32_t* row_ptr, const int32_t* dst, const int32_t* col,
+                               const float* attr /*[E,k]*/, const float* rvec,
+                               const float* h_in /*[N,H]*/, const float* v_in /*[N,3]*/,
+                               const float* W, float* h_out /*[N,H]*/, float* v_out /*[N,3]*/,
+                               void* saved, size_t saved_bytes, void* ws, size_t ws_bytes);
+
+int32_t hgnn_mp_layer_attr_bwd(void* stream, int32_t N, int64_t E, int32_t H, int32_t k, int32_t dtype, float alpha,
+                               const int32_t* row_ptr, const int32_t* dst, const int32_t* col,
+                               const float* attr /*[E,k]*/, const float* rvec,
+                               const int32_t* colT_ptr, const int32_t* permT,
+                               const float* h_in, const float* W, const void* saved, size_t saved_bytes,
+                               const float* g_h_out /*[N,H]*/, const float* g_v_out /*[N,3]*/,
+                               float* g_h_in /*out [N,H]*/, float* g_v_in /*out [N,3]*/,
+                               float* gW /*out, layout of W*/, void* ws, size_t ws_bytes);
+
+/* ---------------------------------------------------------------------------------------------
  * Pooling over the contiguous atoms of each graph: p_g = sum or mean of h_i (mean gives the
  * "energy per atom" target of the paper its per-atom normalisation). Empty graphs give 0.
  * _bwd: g_h_i (+)= g_p[g(i)] (/ n_g);  accumulate != 0 adds into g_h instead of overwriting it.

@@ -21,6 +21,7 @@ EXPORTS = [
     "hgnn_radius_graph_workspace_bytes", "hgnn_radius_graph_count", "hgnn_radius_graph_fill",
     "hgnn_embed_fwd", "hgnn_embed_bwd", "hgnn_embed_bwd_workspace_bytes",
     "hgnn_set_side_stream", "hgnn_mp_layer_workspace_bytes", "hgnn_mp_layer_fwd", "hgnn_mp_layer_bwd",
+    "hgnn_edge_rbf", "hgnn_mp_layer_attr_workspace_bytes", "hgnn_mp_layer_attr_fwd", "hgnn_mp_layer_attr_bwd",
     "hgnn_pool_by_graph_fwd", "hgnn_pool_by_graph_bwd",
     "hgnn_multihead_plan_ints", "hgnn_multihead_plan",
     "hgnn_multihead_decode_workspace_bytes", "hgnn_multihead_decode_fwd", "hgnn_multihead_decode_bwd",
@@ -72,6 +73,12 @@ _mp_fwd = _sig("hgnn_mp_layer_fwd", vp, i32, i64, i32, i32, f32, vp, vp, vp, vp,
                vp, sz, vp, sz)
 _mp_bwd = _sig("hgnn_mp_layer_bwd", vp, i32, i64, i32, i32, f32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz,
                vp, vp, vp, vp, vp, vp, sz)
+_rbf = _sig("hgnn_edge_rbf", vp, i64, vp, i32, f32, vp)
+_mpa_ws = _sig("hgnn_mp_layer_attr_workspace_bytes", i32, i64, i32, i32, i32, C.POINTER(sz), C.POINTER(sz))
+_mpa_fwd = _sig("hgnn_mp_layer_attr_fwd", vp, i32, i64, i32, i32, i32, f32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
+                vp, sz, vp, sz)
+_mpa_bwd = _sig("hgnn_mp_layer_attr_bwd", vp, i32, i64, i32, i32, i32, f32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz,
+                vp, vp, vp, vp, vp, vp, sz)
 _adamw = _sig("hgnn_adamw_step", vp, i64, vp, vp, vp, vp, i32, C.c_double, C.c_double, C.c_double, C.c_double,
               C.c_double)
 _pool_fwd = _sig("hgnn_pool_by_graph_fwd", vp, i32, i32, i32, i32, vp, vp, vp)
@@ -163,6 +170,28 @@ def mp_layer_workspace_bytes(N, E, H, dtype):
     a, b = sz(0), sz(0)
     _check(_mp_ws(N, E, H, dtype, C.byref(a), C.byref(b)))
     return a.value, b.value
+
+
+def edge_rbf(E, d2, k, rc, attr):
+    _check(_rbf(_stream(), E, _p(d2), k, rc, _p(attr)))
+
+
+def mp_layer_attr_workspace_bytes(N, E, H, k, dtype):
+    a, b = sz(0), sz(0)
+    _check(_mpa_ws(N, E, H, k, dtype, C.byref(a), C.byref(b)))
+    return a.value, b.value
+
+
+def mp_layer_attr_fwd(N, E, H, k, dtype, alpha, row_ptr, dst, col, attr, rvec, h_in, v_in, W, h_out, v_out, saved, ws):
+    _check(_mpa_fwd(_stream(), N, E, H, k, dtype, alpha, _p(row_ptr), _p(dst), _p(col), _p(attr), _p(rvec),
+                    _p(h_in), _p(v_in), _p(W), _p(h_out), _p(v_out), _p(saved), _nbytes(saved), _p(ws), _nbytes(ws)))
+
+
+def mp_layer_attr_bwd(N, E, H, k, dtype, alpha, row_ptr, dst, col, attr, rvec, colT_ptr, permT, h_in, W, saved,
+                      g_h_out, g_v_out, g_h_in, g_v_in, gW, ws):
+    _check(_mpa_bwd(_stream(), N, E, H, k, dtype, alpha, _p(row_ptr), _p(dst), _p(col), _p(attr), _p(rvec),
+                    _p(colT_ptr), _p(permT), _p(h_in), _p(W), _p(saved), _nbytes(saved), _p(g_h_out), _p(g_v_out),
+                    _p(g_h_in), _p(g_v_in), _p(gW), _p(ws), _nbytes(ws)))
 
 
 def mp_layer_fwd(N, E, H, dtype, alpha, row_ptr, dst, col, d2, rvec, h_in, v_in, W, h_out, v_out, saved, ws):

@@ -149,7 +149,7 @@ extern "C" int32_t hgnn_mp_layer_workspace_bytes(int32_t N, int64_t E, int32_t H
   HGNN_TRY(check_layer_args(N, E, H, dtype));
   HGNN_REQUIRE(ws_bytes_host && saved_bytes_host, HGNN_ERR_NULLPTR, "null size pointer");
   if (wide_H(H)) {
-    wide_layer_sizes(N, E, H, ws_bytes_host, saved_bytes_host);
+    wide_layer_sizes(N, E, H, 1, ws_bytes_host, saved_bytes_host);
     return HGNN_OK;
   }
   *ws_bytes_host = carve_ws(nullptr, N, E, H, dtype == HGNN_BF16).bytes;
@@ -172,7 +172,7 @@ extern "C" int32_t hgnn_mp_layer_fwd(void* stream, int32_t N, int64_t E, int32_t
   HGNN_REQUIRE(h_out != h_in, HGNN_ERR_BAD_SHAPE, "h_out may not alias h_in");
   if (wide_H(H)) {
     size_t need_ws, need_saved;
-    wide_layer_sizes(N, E, H, &need_ws, &need_saved);
+    wide_layer_sizes(N, E, H, 1, &need_ws, &need_saved);
     HGNN_REQUIRE(ws_bytes >= need_ws, HGNN_ERR_WORKSPACE_TOO_SMALL, "mp_layer workspace: need %zu bytes, got %zu", need_ws, ws_bytes);
     HGNN_REQUIRE(saved_bytes >= need_saved, HGNN_ERR_WORKSPACE_TOO_SMALL, "mp_layer saved buffer: need %zu bytes, got %zu", need_saved, saved_bytes);
     WideLayerArgs a;
@@ -264,7 +264,7 @@ extern "C" int32_t hgnn_mp_layer_bwd(void* stream, int32_t N, int64_t E, int32_t
   if (N == 0) return launch_fill_f32(st, gW, LayerOff(H).total, 0.f);
   if (wide_H(H)) {
     size_t need_ws, need_saved;
-    wide_layer_sizes(N, E, H, &need_ws, &need_saved);
+    wide_layer_sizes(N, E, H, 1, &need_ws, &need_saved);
     HGNN_REQUIRE(ws_bytes >= need_ws, HGNN_ERR_WORKSPACE_TOO_SMALL, "mp_layer workspace: need %zu bytes, got %zu", need_ws, ws_bytes);
     HGNN_REQUIRE(saved_bytes >= need_saved, HGNN_ERR_WORKSPACE_TOO_SMALL, "mp_layer saved buffer: need %zu bytes, got %zu", need_saved, saved_bytes);
     WideLayerArgs a;
@@ -395,4 +395,75 @@ extern "C" int32_t hgnn_mp_layer_bwd(void* stream, int32_t N, int64_t E, int32_t
   HGNN_TRY(stream_after(st, sx, ss.ev[4]));   // join: the caller's stream now also orders after every gradient
   if (g_v_in != g_v_out) HGNN_TRY(launch_copy_f32(st, g_v_out, g_v_in, (int64_t)N * 3));
   return HGNN_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// the layer with k edge attributes in place of d2 (fragment path at every width)
+// ---------------------------------------------------------------------------------------------
+static int32_t check_attr_args(int N, int64_t E, int H, int k, int dtype) {
+  HGNN_REQUIRE(N >= 0 && E >= 0, HGNN_ERR_BAD_SHAPE, "negative N or E");
+  HGNN_REQUIRE(E <= 2147483647LL - 256, HGNN_ERR_OVERFLOW, "edge count does not fit the 32-bit edge indices");
+  HGNN_REQUIRE(dtype == HGNN_F32 || dtype == HGNN_BF16, HGNN_ERR_BAD_SHAPE, "unknown dtype %d", dtype);
+  HGNN_REQUIRE(H >= 1 && H <= 1024, HGNN_ERR_BAD_SHAPE, "H must lie in 1..1024 (got %d)", H);
+  HGNN_REQUIRE(k >= 1 && k <= WIDE_MAX_ATTR, HGNN_ERR_BAD_SHAPE, "k must lie in 1..%d (got %d)", WIDE_MAX_ATTR, k);
+  HGNN_REQUIRE(dtype == HGNN_BF16, HGNN_ERR_UNIMPLEMENTED, "layers with edge attributes run with bf16 operands only");
+  return HGNN_OK;
+}
+
+extern "C" int32_t hgnn_mp_layer_attr_workspace_bytes(int32_t N, int64_t E, int32_t H, int32_t k, int32_t dtype,
+                                                      size_t* ws_bytes_host, size_t* saved_bytes_host) {
+  HGNN_TRY(check_attr_args(N, E, H, k, dtype));
+  HGNN_REQUIRE(ws_bytes_host && saved_bytes_host, HGNN_ERR_NULLPTR, "null size pointer");
+  wide_layer_sizes(N, E, H, k, ws_bytes_host, saved_bytes_host);
+  return HGNN_OK;
+}
+
+extern "C" int32_t hgnn_mp_layer_attr_fwd(void* stream, int32_t N, int64_t E, int32_t H, int32_t k, int32_t dtype,
+                                          float alpha, const int32_t* row_ptr, const int32_t* dst, const int32_t* col,
+                                          const float* attr, const float* rvec, const float* h_in, const float* v_in,
+                                          const float* W, float* h_out, float* v_out, void* saved, size_t saved_bytes,
+                                          void* ws, size_t ws_bytes) {
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  HGNN_TRY(check_attr_args(N, E, H, k, dtype));
+  if (N == 0) return HGNN_OK;
+  HGNN_REQUIRE(row_ptr && h_in && v_in && W && h_out && v_out && ws && saved, HGNN_ERR_NULLPTR, "mp_layer_attr_fwd: null pointer");
+  HGNN_REQUIRE(E == 0 || (dst && col && attr && rvec), HGNN_ERR_NULLPTR, "mp_layer_attr_fwd: null edge array");
+  HGNN_REQUIRE(h_out != h_in, HGNN_ERR_BAD_SHAPE, "h_out may not alias h_in");
+  size_t need_ws, need_saved;
+  wide_layer_sizes(N, E, H, k, &need_ws, &need_saved);
+  HGNN_REQUIRE(ws_bytes >= need_ws, HGNN_ERR_WORKSPACE_TOO_SMALL, "mp_layer workspace: need %zu bytes, got %zu", need_ws, ws_bytes);
+  HGNN_REQUIRE(saved_bytes >= need_saved, HGNN_ERR_WORKSPACE_TOO_SMALL, "mp_layer saved buffer: need %zu bytes, got %zu", need_saved, saved_bytes);
+  WideLayerArgs a;
+  a.N = N; a.E = E; a.H = H; a.alpha = alpha;
+  a.row_ptr = row_ptr; a.dst = dst; a.col = col; a.attr = attr; a.k = k; a.rvec = rvec;
+  a.h_in = h_in; a.v_in = v_in; a.W = W; a.h_out = h_out; a.v_out = v_out;
+  a.saved = saved; a.ws = ws;
+  return wide_layer_fwd(st, a);
+}
+
+extern "C" int32_t hgnn_mp_layer_attr_bwd(void* stream, int32_t N, int64_t E, int32_t H, int32_t k, int32_t dtype,
+                                          float alpha, const int32_t* row_ptr, const int32_t* dst, const int32_t* col,
+                                          const float* attr, const float* rvec, const int32_t* colT_ptr,
+                                          const int32_t* permT, const float* h_in, const float* W, const void* saved,
+                                          size_t saved_bytes, const float* g_h_out, const float* g_v_out, float* g_h_in,
+                                          float* g_v_in, float* gW, void* ws, size_t ws_bytes) {
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  HGNN_TRY(check_attr_args(N, E, H, k, dtype));
+  HGNN_REQUIRE(gW && W && ws, HGNN_ERR_NULLPTR, "mp_layer_attr_bwd: null pointer");
+  HGNN_REQUIRE(N == 0 || (row_ptr && colT_ptr && h_in && saved && g_h_out && g_v_out && g_h_in && g_v_in),
+               HGNN_ERR_NULLPTR, "mp_layer_attr_bwd: null pointer");
+  HGNN_REQUIRE(E == 0 || (dst && col && attr && rvec && permT), HGNN_ERR_NULLPTR, "mp_layer_attr_bwd: null edge array");
+  HGNN_REQUIRE(N == 0 || g_h_in != g_h_out, HGNN_ERR_BAD_SHAPE, "g_h_in may not alias g_h_out");
+  if (N == 0) return launch_fill_f32(st, gW, 6L * H * H + (5L + k) * H, 0.f);
+  size_t need_ws, need_saved;
+  wide_layer_sizes(N, E, H, k, &need_ws, &need_saved);
+  HGNN_REQUIRE(ws_bytes >= need_ws, HGNN_ERR_WORKSPACE_TOO_SMALL, "mp_layer workspace: need %zu bytes, got %zu", need_ws, ws_bytes);
+  HGNN_REQUIRE(saved_bytes >= need_saved, HGNN_ERR_WORKSPACE_TOO_SMALL, "mp_layer saved buffer: need %zu bytes, got %zu", need_saved, saved_bytes);
+  WideLayerArgs a;
+  a.N = N; a.E = E; a.H = H; a.alpha = alpha;
+  a.row_ptr = row_ptr; a.dst = dst; a.col = col; a.attr = attr; a.k = k; a.rvec = rvec;
+  a.colT_ptr = colT_ptr; a.permT = permT;
+  a.h_in = h_in; a.W = W; a.g_h_out = g_h_out; a.g_v_out = g_v_out; a.g_h_in = g_h_in; a.g_v_in = g_v_in; a.gW = gW;
+  a.saved = const_cast<void*>(saved); a.ws = ws;
+  return wide_layer_bwd(st, a);
 }

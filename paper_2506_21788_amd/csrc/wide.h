@@ -32,6 +32,8 @@ struct WideLayerArgs {
   const int32_t* dst = nullptr;
   const int32_t* col = nullptr;
   const float* d2 = nullptr;
+  const float* attr = nullptr;   // [E, k] edge attributes in place of d2 (null: d2, k = 1)
+  int k = 1;
   const float* rvec = nullptr;
   const int32_t* colT_ptr = nullptr;
   const int32_t* permT = nullptr;
@@ -49,7 +51,8 @@ struct WideLayerArgs {
   void* ws = nullptr;
 };
 
-void wide_layer_sizes(int N, int64_t E, int H, size_t* ws_bytes, size_t* saved_bytes);
+constexpr int WIDE_MAX_ATTR = 16;   // most edge attributes per edge
+void wide_layer_sizes(int N, int64_t E, int H, int k, size_t* ws_bytes, size_t* saved_bytes);
 int32_t wide_layer_fwd(hipStream_t st, const WideLayerArgs& a);
 int32_t wide_layer_bwd(hipStream_t st, const WideLayerArgs& a);
 

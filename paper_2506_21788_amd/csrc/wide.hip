@@ -544,9 +544,10 @@ struct EdgeElemArgs {
   int H = 0, Hp = 0;
   const int32_t* dst = nullptr;
   const int32_t* col = nullptr;
-  const float* d2 = nullptr;
+  const float* attr = nullptr;          // [E, k] edge attributes (k = 1: the squared distance d2)
+  int k = 1;
   const unsigned short* PQ = nullptr;   // [N, 2 Hp] bf16 row-major: P | Q
-  const float* w1d = nullptr;           // [H]
+  const float* w1d = nullptr;           // [k, H]: the rows of W1 that act on the attributes
   char* a1_R = nullptr;
   char* a1_T = nullptr;
   // reverse
@@ -560,7 +561,7 @@ struct EdgeElemArgs {
   char* gz2_T = nullptr;
   const char* ga1_T = nullptr;          // g_a1
   unsigned short* gz1_rm = nullptr;     // g_z1, bf16 row-major [rows, Hp]: what the two per-atom sums read
-  float* colpart = nullptr;             // [gridDim.y][2][Hp] column-sum partials
+  float* colpart = nullptr;             // [gridDim.y][2 (g_z2) or 1 + k (g_z1)][Hp] column-sum partials
 };
 
 __device__ __forceinline__ void unpack8(const uint4 w, float (&f)[8]) {
@@ -577,24 +578,36 @@ __device__ __forceinline__ uint4 pack8(const float (&f)[8]) {
 enum { EE_A1 = 0, EE_GZ2 = 1, EE_GZ1 = 2 };
 constexpr int EE_PITCH = 136;   // LDS tile row pitch in bf16 elements (128 + 8: 16-byte reads of a column of rows spread over the banks)
 
-// EE_A1:  a1 = silu(P[dst] + Q[col] + d2 w1d)                                   -> R and T
+// EE_A1:  a1 = silu(z1), z1 = P[dst] + Q[col] + sum_j attr_j w1d_j               -> R and T
 // EE_GZ2: g_z2 = (alpha g_M[dst] + c_e wx) silu'(z2)                            -> R and T; sums: g_b2 = sum g_z2, g_wx = sum c_e silu(z2)
-// EE_GZ1: g_z1 = g_a1 silu'(z1), z1 recomputed from the gathers                 -> row-major; sums: g_b1 = sum g_z1, g_w1d = sum d2 g_z1
-template <int MODE>
+// EE_GZ1: g_z1 = g_a1 silu'(z1), z1 recomputed from the gathers                 -> row-major; sums: g_b1 = sum g_z1, g_w1d_j = sum attr_j g_z1
+// KMAX: most edge attributes the instance handles (1: the squared distance alone; 16: p.k of them, p.k <= 16)
+template <int MODE, int KMAX>
 __global__ void __launch_bounds__(256) k_edge_elem(EdgeElemArgs p) {
+  constexpr int NV = MODE == EE_GZ1 ? 1 + KMAX : 2;   // column sums kept per column
   __shared__ __align__(16) unsigned short tile[32 * EE_PITCH];
-  __shared__ float csum[4][2][128];
+  __shared__ float csum[4][NV][128];
   const int tid = threadIdx.x, x = tid & 63;
   const int q = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int slab = blockIdx.x;
   const int c = slab * 128 + 2 * x;       // this thread's columns: c, c + 1
   const int ncb = p.Hp >> 5, nkb = p.Hp >> 4;
   const int hh = q >> 1, g = q & 1;
-  const float* wv = MODE == EE_GZ2 ? p.wx : p.w1d;
-  const float w0 = c < p.H ? wv[c] : 0.f, w1 = c + 1 < p.H ? wv[c + 1] : 0.f;
+  // wx of this thread's two columns (g_z2), or the rows of W1 that act on the edge attributes
+  float w0[KMAX], w1[KMAX];
+#pragma unroll
+  for (int j = 0; j < KMAX; ++j) {
+    const float* wv = MODE == EE_GZ2 ? p.wx : p.w1d + (long)j * p.H;
+    const bool on = MODE == EE_GZ2 ? j == 0 : j < p.k;
+    w0[j] = on && c < p.H ? wv[c] : 0.f;
+    w1[j] = on && c + 1 < p.H ? wv[c + 1] : 0.f;
+  }
   const long lastrow = p.E > 0 ? p.E - 1 : 0;
   char* Tdst = MODE == EE_A1 ? p.a1_T : p.gz2_T;
-  float s00 = 0.f, s01 = 0.f, s10 = 0.f, s11 = 0.f;   // [sum][column]
+  float s00 = 0.f, s01 = 0.f;          // column sums of the result
+  float s10[KMAX], s11[KMAX];          // weighted column sums
+#pragma unroll
+  for (int j = 0; j < KMAX; ++j) { s10[j] = 0.f; s11[j] = 0.f; }
   for (int rb = blockIdx.y; rb < p.nrb; rb += gridDim.y) {
     const int rb16 = 2 * rb + hh;
     // the two columns are neighbouring 16-byte slots of one half fragment
@@ -610,19 +623,21 @@ __global__ void __launch_bounds__(256) k_edge_elem(EdgeElemArgs p) {
     }
     unsigned ga[8], gb[8];
     float sc[8];
+    long rrow[8];
     bool ok[8];
 #pragma unroll
     for (int u = 0; u < 8; ++u) {
       const long r = tset_row(rb16, g, u);     // the same for all lanes of the wavefront
       ok[u] = r < p.E;
       const long rr = ok[u] ? r : lastrow;
+      rrow[u] = rr;
       const long di = p.dst[rr];
       if (MODE == EE_GZ2) {
         sc[u] = p.cvec[rr];
         ga[u] = *reinterpret_cast<const unsigned*>(p.gM + di * p.ldgM + c);
       } else {
         const long ci = p.col[rr];
-        sc[u] = p.d2[rr];
+        if (KMAX == 1) sc[u] = p.attr[rr];
         ga[u] = *reinterpret_cast<const unsigned*>(p.PQ + di * 2 * p.Hp + c);
         gb[u] = *reinterpret_cast<const unsigned*>(p.PQ + ci * 2 * p.Hp + p.Hp + c);
       }
@@ -636,15 +651,27 @@ __global__ void __launch_bounds__(256) k_edge_elem(EdgeElemArgs p) {
         float y0, d0, y1, d1;
         silu_both(x0, y0, d0);
         silu_both(x1, y1, d1);
-        const float gz0 = ok[u] ? fmaf(sc[u], w0, p.alpha * bf_lo(ga[u])) * d0 : 0.f;
-        const float gz1 = ok[u] ? fmaf(sc[u], w1, p.alpha * bf_hi(ga[u])) * d1 : 0.f;
+        const float gz0 = ok[u] ? fmaf(sc[u], w0[0], p.alpha * bf_lo(ga[u])) * d0 : 0.f;
+        const float gz1 = ok[u] ? fmaf(sc[u], w1[0], p.alpha * bf_hi(ga[u])) * d1 : 0.f;
         s00 += gz0; s01 += gz1;
-        s10 += ok[u] ? sc[u] * y0 : 0.f;
-        s11 += ok[u] ? sc[u] * y1 : 0.f;
+        s10[0] += ok[u] ? sc[u] * y0 : 0.f;
+        s11[0] += ok[u] ? sc[u] * y1 : 0.f;
         o0[u] = gz0; o1[u] = gz1;
       } else {
-        const float z0 = bf_lo(ga[u]) + bf_lo(gb[u]) + sc[u] * w0;
-        const float z1 = bf_hi(ga[u]) + bf_hi(gb[u]) + sc[u] * w1;
+        // the attributes of the row (the same for all lanes of the wavefront)
+        float at[KMAX];
+        if (KMAX == 1) {
+          at[0] = sc[u];
+        } else {
+#pragma unroll
+          for (int j = 0; j < KMAX; ++j) at[j] = j < p.k ? p.attr[rrow[u] * p.k + j] : 0.f;
+        }
+        float z0 = bf_lo(ga[u]) + bf_lo(gb[u]), z1 = bf_hi(ga[u]) + bf_hi(gb[u]);
+#pragma unroll
+        for (int j = 0; j < KMAX; ++j) {
+          z0 = fmaf(at[j], w0[j], z0);
+          z1 = fmaf(at[j], w1[j], z1);
+        }
         if (MODE == EE_A1) {
           o0[u] = ok[u] ? silu_f(z0) : 0.f;
           o1[u] = ok[u] ? silu_f(z1) : 0.f;
@@ -652,8 +679,11 @@ __global__ void __launch_bounds__(256) k_edge_elem(EdgeElemArgs p) {
           const float gz0 = ok[u] ? x0 * dsilu_f(z0) : 0.f;
           const float gz1 = ok[u] ? x1 * dsilu_f(z1) : 0.f;
           s00 += gz0; s01 += gz1;
-          s10 += ok[u] ? sc[u] * gz0 : 0.f;
-          s11 += ok[u] ? sc[u] * gz1 : 0.f;
+#pragma unroll
+          for (int j = 0; j < KMAX; ++j) {
+            s10[j] = fmaf(at[j], gz0, s10[j]);
+            s11[j] = fmaf(at[j], gz1, s11[j]);
+          }
           o0[u] = gz0; o1[u] = gz1;
         }
       }
@@ -698,12 +728,15 @@ __global__ void __launch_bounds__(256) k_edge_elem(EdgeElemArgs p) {
   if (MODE != EE_A1) {
     // column sums of the workgroup: the four row sets are added in order
     csum[q][0][2 * x] = s00; csum[q][0][2 * x + 1] = s01;
-    csum[q][1][2 * x] = s10; csum[q][1][2 * x + 1] = s11;
+#pragma unroll
+    for (int j = 0; j < NV - 1; ++j) { csum[q][1 + j][2 * x] = s10[j]; csum[q][1 + j][2 * x + 1] = s11[j]; }
     __syncthreads();
+    const int nv = MODE == EE_GZ2 ? 2 : 1 + p.k;
     if (tid < 128) {
-      float* o = p.colpart + (long)blockIdx.y * 2 * p.Hp + slab * 128 + tid;
-      o[0] = ((csum[0][0][tid] + csum[1][0][tid]) + csum[2][0][tid]) + csum[3][0][tid];
-      o[p.Hp] = ((csum[0][1][tid] + csum[1][1][tid]) + csum[2][1][tid]) + csum[3][1][tid];
+      float* o = p.colpart + (long)blockIdx.y * nv * p.Hp + slab * 128 + tid;
+#pragma unroll
+      for (int j = 0; j < NV; ++j)
+        if (j < nv) o[(long)j * p.Hp] = ((csum[0][j][tid] + csum[1][j][tid]) + csum[2][j][tid]) + csum[3][j][tid];
     }
   }
 }
@@ -856,9 +889,9 @@ static int32_t launch_seg_fwd_w(hipStream_t st, int Hp, int N, const int32_t* ro
 // host side
 // ---------------------------------------------------------------------------------------------
 struct WideDims {
-  int N, H, Hp, Np, ncb, nkb;
+  int N, H, Hp, Np, ncb, nkb, k;
   int64_t E, Ep;
-  WideDims(int N_, int64_t E_, int H_) : N(N_), H(H_), E(E_) {
+  WideDims(int N_, int64_t E_, int H_, int k_) : N(N_), H(H_), k(k_), E(E_) {
     Hp = wide_pad_cols(H);
     Np = (int)wide_pad_rows(N);
     Ep = wide_pad_rows(E);
@@ -871,9 +904,9 @@ struct WideDims {
 
 struct LayerOffW {
   long W1, b1, W2, b2, wx, W3, b3, W4, b4, total;
-  explicit LayerOffW(long H) {
+  LayerOffW(long H, long k) {   // k edge attributes: W1 has 2H + k rows
     long o = 0;
-    W1 = o; o += (2 * H + 1) * H;
+    W1 = o; o += (2 * H + k) * H;
     b1 = o; o += H;
     W2 = o; o += H * H;
     b2 = o; o += H;
@@ -954,7 +987,7 @@ static WideWs carve_ws_w(void* p, const WideDims& d) {
   w.ga1_T = c.take<char>(d.edge_bytes());
   w.cvec = c.take<float>((size_t)d.E + 4);
   w.colpart = c.take<float>((size_t)ELEM_MAX_BLOCKS * 2 * d.Hp);
-  w.colpart2 = c.take<float>((size_t)ELEM_MAX_BLOCKS * 2 * d.Hp);
+  w.colpart2 = c.take<float>((size_t)ELEM_MAX_BLOCKS * (1 + d.k) * d.Hp);
   w.cs_partial = c.take<float>(colsum_rows_partial_floats(d.N, d.Hp, 1));
   w.partial_floats = (size_t)24 * 2 * d.Hp * d.Hp;
   w.partial = c.take<float>(w.partial_floats);
@@ -964,8 +997,8 @@ static WideWs carve_ws_w(void* p, const WideDims& d) {
   return w;
 }
 
-void wide_layer_sizes(int N, int64_t E, int H, size_t* ws_bytes, size_t* saved_bytes) {
-  const WideDims d(N, E, H);
+void wide_layer_sizes(int N, int64_t E, int H, int k, size_t* ws_bytes, size_t* saved_bytes) {
+  const WideDims d(N, E, H, k);
   *ws_bytes = carve_ws_w(nullptr, d).bytes;
   *saved_bytes = carve_saved_w(nullptr, d).bytes;
 }
@@ -1061,11 +1094,12 @@ static int32_t colsum_w(hipStream_t st, const float* X, long ldx, const float* Z
 }
 
 int32_t wide_layer_fwd(hipStream_t st, const WideLayerArgs& a) {
-  const WideDims d(a.N, a.E, a.H);
+  const int k = a.k;   // edge attributes: a.attr [E, k], or d2 alone (k = 1) when a.attr is null
+  const WideDims d(a.N, a.E, a.H, k);
   const int H = d.H, Hp = d.Hp;
   WideWs w = carve_ws_w(a.ws, d);
   WideSaved s = carve_saved_w(a.saved, d);
-  const LayerOffW o(H);
+  const LayerOffW o(H, k);
   const long HH = (long)H * H, PP = (long)Hp * Hp;
   const float* W = a.W;
 
@@ -1099,12 +1133,13 @@ int32_t wide_layer_fwd(hipStream_t st, const WideLayerArgs& a) {
   }
   EdgeElemArgs e;
   e.E = d.E; e.nrb = (int)(d.Ep / 32); e.H = H; e.Hp = Hp;
-  e.dst = a.dst; e.col = a.col; e.d2 = a.d2; e.PQ = s.PQ; e.w1d = W + o.W1 + 2 * HH;
+  e.dst = a.dst; e.col = a.col; e.attr = a.attr ? a.attr : a.d2; e.k = k; e.PQ = s.PQ; e.w1d = W + o.W1 + 2 * HH;
   e.a1_R = s.a1_R; e.a1_T = s.a1_T;
   if (d.Ep > 0) {
     {
       ProfScope ps(PT_EDGE_ELEM, st);
-      k_edge_elem<EE_A1><<<elem_grid(e.nrb, Hp), 256, 0, st>>>(e);
+      if (k == 1) k_edge_elem<EE_A1, 1><<<elem_grid(e.nrb, Hp), 256, 0, st>>>(e);
+      else k_edge_elem<EE_A1, 16><<<elem_grid(e.nrb, Hp), 256, 0, st>>>(e);
       HGNN_LAUNCH_CHECK("k_edge_elem (a1)");
     }
     // z2 = a1 W2 + b2 (T fragments)
@@ -1145,11 +1180,12 @@ int32_t wide_layer_fwd(hipStream_t st, const WideLayerArgs& a) {
 }
 
 int32_t wide_layer_bwd(hipStream_t st, const WideLayerArgs& a) {
-  const WideDims d(a.N, a.E, a.H);
+  const int k = a.k;   // edge attributes: a.attr [E, k], or d2 alone (k = 1) when a.attr is null
+  const WideDims d(a.N, a.E, a.H, k);
   const int H = d.H, Hp = d.Hp;
   WideWs w = carve_ws_w(a.ws, d);
   WideSaved s = carve_saved_w(a.saved, d);
-  const LayerOffW o(H);
+  const LayerOffW o(H, k);
   const long HH = (long)H * H, PP = (long)Hp * Hp;
   const float* W = a.W;
   float* gW = a.gW;
@@ -1211,7 +1247,7 @@ int32_t wide_layer_bwd(hipStream_t st, const WideLayerArgs& a) {
   // edge part
   EdgeElemArgs e;
   e.E = d.E; e.nrb = (int)(d.Ep / 32); e.H = H; e.Hp = Hp;
-  e.dst = a.dst; e.col = a.col; e.d2 = a.d2; e.PQ = s.PQ; e.w1d = W + o.W1 + 2 * HH;
+  e.dst = a.dst; e.col = a.col; e.attr = a.attr ? a.attr : a.d2; e.k = k; e.PQ = s.PQ; e.w1d = W + o.W1 + 2 * HH;
   e.z2_T = s.z2_T; e.gM = w.gM_b + Hp; e.ldgM = 2 * Hp; e.cvec = w.cvec; e.wx = W + o.wx; e.alpha = a.alpha;
   e.gz2_R = w.gz2_R; e.gz2_T = w.gz2_T; e.ga1_T = w.ga1_T; e.colpart = w.colpart;
   e.gz1_rm = reinterpret_cast<unsigned short*>(w.gz2_R);   // free again once g_a1 has been formed
@@ -1220,7 +1256,7 @@ int32_t wide_layer_bwd(hipStream_t st, const WideLayerArgs& a) {
   HGNN_TRY(launch_edge_cvec(st, d.E, a.dst, a.rvec, a.g_v_out, a.alpha, w.cvec));
   {
     ProfScope ps(PT_EDGE_ELEM, st);
-    k_edge_elem<EE_GZ2><<<egrid, 256, 0, st>>>(e);
+    k_edge_elem<EE_GZ2, 1><<<egrid, 256, 0, st>>>(e);
     HGNN_LAUNCH_CHECK("k_edge_elem (g_z2)");
   }
   HGNN_TRY(stream_after(sx, st, ss.ev[2]));
@@ -1240,7 +1276,8 @@ int32_t wide_layer_bwd(hipStream_t st, const WideLayerArgs& a) {
   e.colpart = w.colpart2;
   {
     ProfScope ps(PT_EDGE_ELEM, st);
-    k_edge_elem<EE_GZ1><<<egrid, 256, 0, st>>>(e);
+    if (k == 1) k_edge_elem<EE_GZ1, 1><<<egrid, 256, 0, st>>>(e);
+    else k_edge_elem<EE_GZ1, 16><<<egrid, 256, 0, st>>>(e);
     HGNN_LAUNCH_CHECK("k_edge_elem (g_z1)");
   }
   // g_P, g_Q: per-atom sums of g_z1 over the destination-sorted and the source-sorted lists
@@ -1264,8 +1301,9 @@ int32_t wide_layer_bwd(hipStream_t st, const WideLayerArgs& a) {
   HGNN_TRY(stream_after(sx, st, ss.ev[3]));
   {  // side: g_b1, g_w1d from the g_z1 kernel's column sums; g_W1a = h^T g_P, g_W1b = h^T g_Q
     ProfScope ps(PT_COLSUM, sx);
-    HGNN_TRY(launch_reduce_cols(sx, w.colpart2, eg, 2 * Hp, H, gW + o.b1));
-    HGNN_TRY(launch_reduce_cols(sx, w.colpart2 + Hp, eg, 2 * Hp, H, gW + o.W1 + 2 * HH));
+    HGNN_TRY(launch_reduce_cols(sx, w.colpart2, eg, (long)(1 + k) * Hp, H, gW + o.b1));
+    // the k rows of W1 that act on the edge attributes: one group per row
+    HGNN_TRY(launch_reduce_cols(sx, w.colpart2 + Hp, eg, (long)(1 + k) * Hp, H, gW + o.W1 + 2 * HH, k, Hp, H));
   }
   HGNN_TRY(wgrad_w(sx, d, s.hM_T, 2 * d.ncb, 0, d.ncb, w.gPQ_T, 2 * d.ncb, 0, 2 * d.ncb, d.Np, w.partial, w.partial_floats,
                    gW + o.W1, 0, HH, PT_WGRAD_NODE));

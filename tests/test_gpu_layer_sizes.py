@@ -82,3 +82,76 @@ def test_layer_other_modes_edge_counts(H, dtype, E):
                                    (500, 64, 256), (866, 5, 17), (333, 100, 1500), (257, 33, 700), (100, 80, 900), (24, 50, 300)])
 def test_layer_wide_widths(H, N, E):
     _run_layer(N=N, E=E, H=H, dtype="bf16", seed=H + E)
+
+
+# ------------------------------------------------------------------------------------------------
+# k edge attributes (radial basis of the edge length) in place of d2
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("E,k,rc", [(5000, 8, 5.0), (1, 2, 3.0), (777, 16, 6.0), (0, 4, 5.0)])
+def test_edge_rbf_matches_the_oracle(E, k, rc):
+    import torch
+    from paper_2506_21788_amd import binding as B
+    rng = np.random.default_rng(E + k)
+    d = rng.uniform(0.0, rc, size=E).astype(np.float32)
+    if E > 3:
+        d[:3] = (0.0, rc, np.float32(rc) * np.float32(0.999999))
+    d2 = (d * d).astype(np.float32)
+    attr = torch.full((max(E, 1), k), float("nan"), dtype=torch.float32, device="cuda")
+    B.edge_rbf(E, torch.as_tensor(d2).cuda(), k, rc, attr)
+    torch.cuda.synchronize()
+    if E == 0:
+        return
+    want = oracle.edge_rbf(d2, k, rc)
+    got = attr.cpu().numpy()[:E]
+    assert np.all(np.isfinite(got))
+    assert relerr(got, want) <= TOL["f32"]["fwd"]      # float32 arithmetic against the float64 definition
+
+
+def _run_layer_attr(N, E, H, k, seed, rc=5.0):
+    import torch
+    from paper_2506_21788_amd import binding as B
+    rng = np.random.default_rng(seed)
+    row_ptr, dst, col, d2, rvec = _edges(rng, N, E)
+    d2 = np.minimum(d2, np.float32(rc * rc))
+    attr = oracle.edge_rbf(d2, k, rc).astype(np.float32) if k > 1 else d2[:, None].copy()
+    colT_ptr, permT = oracle.transpose_plan(col, N)
+    W = init_layer_weights(rng, H, k=k).astype(np.float32)
+    h = rng.standard_normal((N, H)).astype(np.float32)
+    v = (rng.standard_normal((N, 3)) * 0.3).astype(np.float32)
+    gh = rng.standard_normal((N, H)).astype(np.float32)
+    gv = rng.standard_normal((N, 3)).astype(np.float32)
+    alpha = 1.0 / max(1.0, E / N)
+    dev = lambda a: torch.as_tensor(np.ascontiguousarray(a)).cuda()
+    ws_b, saved_b = B.mp_layer_attr_workspace_bytes(N, E, H, k, B.BF16)
+    ws = torch.empty(ws_b, dtype=torch.uint8, device="cuda")
+    saved = torch.empty(saved_b, dtype=torch.uint8, device="cuda")
+    t = dict(row_ptr=dev(row_ptr), dst=dev(dst), col=dev(col), attr=dev(attr), rvec=dev(rvec), colT=dev(colT_ptr),
+             permT=dev(permT.astype(np.int32)), h=dev(h), v=dev(v), W=dev(W), gh=dev(gh), gv=dev(gv))
+    h_out, v_out = torch.empty_like(t["h"]), torch.empty_like(t["v"])
+    g_h, g_v = torch.empty_like(t["h"]), torch.empty_like(t["v"])
+    gW = torch.full_like(t["W"], float("nan"))
+    B.mp_layer_attr_fwd(N, E, H, k, B.BF16, alpha, t["row_ptr"], t["dst"], t["col"], t["attr"], t["rvec"], t["h"],
+                        t["v"], t["W"], h_out, v_out, saved, ws)
+    B.mp_layer_attr_bwd(N, E, H, k, B.BF16, alpha, t["row_ptr"], t["dst"], t["col"], t["attr"], t["rvec"], t["colT"],
+                        t["permT"], t["h"], t["W"], saved, t["gh"], t["gv"], g_h, g_v, gW, ws)
+    torch.cuda.synchronize()
+    ho, vo, cache = oracle.mp_layer_fwd(h, v, dst, col, d2, rvec, W.astype(np.float64), alpha, attr=attr)
+    gho, gvo, gWo = oracle.mp_layer_bwd(cache, gh, gv)
+    tol = TOL["bf16"]
+    errs = dict(h=relerr(h_out.cpu().numpy(), ho), v=relerr(v_out.cpu().numpy(), vo),
+                g_h=relerr(g_h.cpu().numpy(), gho), g_v=relerr(g_v.cpu().numpy(), gvo))
+    got_flat = gW.cpu().numpy()
+    assert np.all(np.isfinite(got_flat)), "a gradient field was left unwritten"
+    got = oracle.unpack_layer(got_flat, H, k)
+    for name, want in gWo.items():
+        errs["gW." + name] = relerr(got[name], want)
+    errs["gW.W1[attr rows]"] = relerr(got["W1"][2 * H:], gWo["W1"][2 * H:])
+    print(f"layer attr N={N} E={E} H={H} k={k}", {n: f"{e:.1e}" for n, e in errs.items()}, flush=True)
+    for n, e in errs.items():
+        assert e <= (tol["fwd"] if n in ("h", "v") else tol["grad"]), (n, e)
+
+
+@pytest.mark.parametrize("N,E,H,k", [(300, 5000, 866, 8), (200, 3001, 256, 16), (100, 1500, 64, 4), (64, 700, 333, 3),
+                                     (50, 0, 128, 5), (120, 2000, 300, 1)])
+def test_layer_with_edge_attributes(N, E, H, k):
+    _run_layer_attr(N=N, E=E, H=H, k=k, seed=H + E + k)
