@@ -63,11 +63,15 @@ class HotPath:
     """One GPU's share of a training step on one batch: graph -> embed -> L layers -> pool -> heads,
     forward and backward. Inputs are numpy arrays (uploaded once); outputs stay on the device."""
 
-    def __init__(self, batch, rc, H, L, S, dtype, emb, layer_weights, head_weights, alpha=None, Hh=None, D=None):
-        """D: hidden layers per head (the deep-head entry points); None: the one-hidden-layer heads."""
+    def __init__(self, batch, rc, H, L, S, dtype, emb, layer_weights, head_weights, alpha=None, Hh=None, D=None,
+                 rbf_k=None):
+        """D: hidden layers per head (the deep-head entry points); None: the one-hidden-layer heads.
+        rbf_k: number of radial-basis edge attributes that take the place of d2 (None: d2 itself)."""
         self.N, self.G, self.H, self.L, self.S = batch.N, batch.G, H, L, S
         self.Hh = H if Hh is None else Hh
         self.D = D
+        self.rbf_k = rbf_k
+        self.rc = float(rc)
         self.dtype = {"f32": B.F32, "bf16": B.BF16}[dtype]
         self.pos = _dev(batch.pos, torch.float32)
         self.Z = _dev(batch.Z, torch.int32)
@@ -97,7 +101,11 @@ class HotPath:
             return
         N, G, H, L, S = self.N, self.G, self.H, self.L, self.S
         f32 = dict(dtype=torch.float32, device="cuda")
-        ws_b, saved_b = B.mp_layer_workspace_bytes(N, E, H, self.dtype)
+        if self.rbf_k is None:
+            ws_b, saved_b = B.mp_layer_workspace_bytes(N, E, H, self.dtype)
+        else:
+            ws_b, saved_b = B.mp_layer_attr_workspace_bytes(N, E, H, self.rbf_k, self.dtype)
+            self.attr = torch.empty((max(E, 1), self.rbf_k), **f32)
         if self.D is None:
             hws_b, hsaved_b = B.multihead_decode_workspace_bytes(N, G, H, self.Hh, S, self.dtype)
         else:
@@ -122,9 +130,16 @@ class HotPath:
     def forward(self):
         g, N, G, H = self.graph, self.N, self.G, self.H
         B.embed_fwd(N, H, self.Z, self.emb, self.h[0])
+        if self.rbf_k is not None:
+            B.edge_rbf(g.E, g.d2, self.rbf_k, self.rc, self.attr)
         for l in range(self.L):
-            B.mp_layer_fwd(N, g.E, H, self.dtype, self.alpha, g.row_ptr, g.dst, g.col, g.d2, g.rvec,
-                           self.h[l], self.v[l], self.W[l], self.h[l + 1], self.v[l + 1], self.saved[l], self.ws)
+            if self.rbf_k is None:
+                B.mp_layer_fwd(N, g.E, H, self.dtype, self.alpha, g.row_ptr, g.dst, g.col, g.d2, g.rvec,
+                               self.h[l], self.v[l], self.W[l], self.h[l + 1], self.v[l + 1], self.saved[l], self.ws)
+            else:
+                B.mp_layer_attr_fwd(N, g.E, H, self.rbf_k, self.dtype, self.alpha, g.row_ptr, g.dst, g.col, self.attr,
+                                    g.rvec, self.h[l], self.v[l], self.W[l], self.h[l + 1], self.v[l + 1],
+                                    self.saved[l], self.ws)
         B.pool_by_graph_fwd(N, G, H, B.POOL_MEAN, self.graph_off, self.h[-1], self.p)
         if self.D is None:
             B.multihead_decode_fwd(N, G, H, self.Hh, self.S, self.dtype, self.plan, self.p, self.h[-1], self.v[-1],
@@ -146,9 +161,14 @@ class HotPath:
         B.pool_by_graph_bwd(N, G, H, B.POOL_MEAN, self.graph_off, self.g_p, self.g_h[0], True)
         cur = 0
         for l in reversed(range(self.L)):
-            B.mp_layer_bwd(N, g.E, H, self.dtype, self.alpha, g.row_ptr, g.dst, g.col, g.d2, g.rvec, g.colT_ptr,
-                           g.permT, self.h[l], self.W[l], self.saved[l], self.g_h[cur], self.g_v[cur],
-                           self.g_h[1 - cur], self.g_v[1 - cur], self.gW[l], self.ws)
+            if self.rbf_k is None:
+                B.mp_layer_bwd(N, g.E, H, self.dtype, self.alpha, g.row_ptr, g.dst, g.col, g.d2, g.rvec, g.colT_ptr,
+                               g.permT, self.h[l], self.W[l], self.saved[l], self.g_h[cur], self.g_v[cur],
+                               self.g_h[1 - cur], self.g_v[1 - cur], self.gW[l], self.ws)
+            else:
+                B.mp_layer_attr_bwd(N, g.E, H, self.rbf_k, self.dtype, self.alpha, g.row_ptr, g.dst, g.col, self.attr,
+                                    g.rvec, g.colT_ptr, g.permT, self.h[l], self.W[l], self.saved[l], self.g_h[cur],
+                                    self.g_v[cur], self.g_h[1 - cur], self.g_v[1 - cur], self.gW[l], self.ws)
             cur = 1 - cur
         B.embed_bwd(N, H, self.Z, self.g_h[cur], self.g_emb, self.ws)
         self.g_h0, self.g_v0 = self.g_h[cur], self.g_v[cur]

@@ -24,13 +24,14 @@ def relerr(a, b):
     return float(num / den) if den > 0 else float(num)
 
 
-def make_weights(seed, H, L, S, N, G, Hh=None, D=None):
-    """Hh, D: head width and hidden layers per head (None: the plain heads, one hidden layer of width H)."""
+def make_weights(seed, H, L, S, N, G, Hh=None, D=None, k=1):
+    """Hh, D: head width and hidden layers per head (None: the plain heads, one hidden layer of width H).
+    k: edge attributes per edge (1: the squared distance)."""
     ss = np.random.SeedSequence(seed).spawn(3)
     rw = np.random.default_rng(ss[1])
     rg = np.random.default_rng(ss[2])
     emb = init_embedding(rw, H)
-    Ws = [init_layer_weights(rw, H) for _ in range(L)]
+    Ws = [init_layer_weights(rw, H, k=k) for _ in range(L)]
     Wh = init_head_weights(rw, H, H, S) if D is None else init_deep_head_weights(rw, H, Hh, D, S)
     gE, gF = upstream_grads(rg, G, N)
     return emb, Ws, Wh, gE, gF
@@ -39,13 +40,15 @@ def make_weights(seed, H, L, S, N, G, Hh=None, D=None):
 def problem_from_config(name, **over):
     batch, hp = make_config(name, **over)
     emb, Ws, Wh, gE, gF = make_weights(hp["seed"], hp["H"], hp["L"], hp["S"], batch.N, batch.G, hp.get("Hh"),
-                                       hp.get("D"))
+                                       hp.get("D"), hp.get("rbf_k") or 1)
     return dict(batch=batch, hp=hp, emb=emb, Ws=Ws, Wh=Wh, gE=gE, gF=gF)
 
 
-def problem_from_batch(batch, rc, H, L, S, dtype, seed=0, Hh=None, D=None):
-    emb, Ws, Wh, gE, gF = make_weights(seed, H, L, S, batch.N, batch.G, Hh, D)
+def problem_from_batch(batch, rc, H, L, S, dtype, seed=0, Hh=None, D=None, rbf_k=None):
+    emb, Ws, Wh, gE, gF = make_weights(seed, H, L, S, batch.N, batch.G, Hh, D, rbf_k or 1)
     hp = dict(rc=rc, H=H, L=L, S=S, dtype=dtype, seed=seed, name="custom")
+    if rbf_k:
+        hp["rbf_k"] = rbf_k
     if D is not None:
         hp.update(Hh=Hh, D=D)
     return dict(batch=batch, hp=hp, emb=emb, Ws=Ws, Wh=Wh, gE=gE, gF=gF)
@@ -58,18 +61,20 @@ def oracle_graph(P):
 
 def oracle_step(P, graph, alpha, grads=True, keep_layers=False):
     b, hp = P["batch"], P["hp"]
+    attr = oracle.edge_rbf(graph["d2"], hp["rbf_k"], hp["rc"]) if hp.get("rbf_k") else None
     return oracle.step_fwd_bwd(b.Z, b.graph_off, b.source_id, graph, P["emb"].astype(np.float64),
                                [w.astype(np.float64) for w in P["Ws"]], P["Wh"].astype(np.float64),
                                hp.get("Hh", hp["H"]), hp["S"], alpha,
                                P["gE"].astype(np.float64) if grads else None,
-                               P["gF"].astype(np.float64) if grads else None, keep_layers=keep_layers, D=hp.get("D"))
+                               P["gF"].astype(np.float64) if grads else None, keep_layers=keep_layers, D=hp.get("D"),
+                               attr=attr)
 
 
 def gpu_hotpath(P, alpha=None):
     from paper_2506_21788_amd.step import HotPath
     b, hp = P["batch"], P["hp"]
     return HotPath(b, hp["rc"], hp["H"], hp["L"], hp["S"], hp["dtype"], P["emb"], P["Ws"], P["Wh"], alpha=alpha,
-                   Hh=hp.get("Hh"), D=hp.get("D"))
+                   Hh=hp.get("Hh"), D=hp.get("D"), rbf_k=hp.get("rbf_k"))
 
 
 def assert_graph_equal(got, want):

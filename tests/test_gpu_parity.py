@@ -444,6 +444,39 @@ def test_step_odd_width_plain_heads():
     compare_step(P, "small H=100 Hh=72 bf16")
 
 
+@pytest.mark.parametrize("H,k", [(128, 8), (866, 16)])
+def test_step_with_radial_basis_edge_attributes(H, k):
+    """Whole step with k radial-basis attributes per edge in place of d2 (every layer gradient field, the W1 rows
+    that act on the attributes included)."""
+    say("step small mixed with radial basis", H, k)
+    b = small_mixed_batch(13, n_mol=5, n_cry=4, S=3, mol_atoms=(3, 40), cry_atoms=(2, 30))
+    P = problem_from_batch(b, 4.5, H, 2, 3, "bf16", seed=H + k, rbf_k=k)
+    import torch
+    hp = P["hp"]
+    tol = TOL["bf16"]
+    og = oracle_graph(P)
+    hpth = gpu_hotpath(P)
+    hpth.build_graph()
+    want = oracle_step(P, og, hpth.alpha, keep_layers=True)
+    hpth.forward()
+    hpth.backward(torch.as_tensor(P["gE"]).cuda(), torch.as_tensor(P["gF"]).cuda())
+    torch.cuda.synchronize()
+    errs = dict(h=relerr(hpth.h[-1].cpu().numpy(), want["h"]), energy=relerr(hpth.energy.cpu().numpy(), want["energy"]),
+                force=relerr(hpth.force.cpu().numpy(), want["force"]))
+    gerrs = dict(g_emb=relerr(hpth.g_emb.cpu().numpy(), want["g_emb"]),
+                 g_heads=relerr(hpth.gWhead.cpu().numpy(), want["g_heads"]))
+    from hgnn_inputs import layer_field_slices
+    for l in range(hp["L"]):
+        got = hpth.gW[l].cpu().numpy()
+        for name, (lo, hi, _) in layer_field_slices(H, k).items():
+            gerrs[f"gW{l}.{name}"] = relerr(got[lo:hi], want["g_layers"][l][lo:hi])
+    say("rbf step", {n: f"{e:.2e}" for n, e in {**errs, **gerrs}.items()})
+    for n, e in errs.items():
+        assert e <= tol["fwd"], (n, e)
+    for n, e in gerrs.items():
+        assert e <= tol["grad"], (n, e)
+
+
 def test_full_size_cfg6_sampled_graphs():
     """Config 6 (128 structures, ~8k atoms, ~250k edges, H = 866, 4 layers, heads 3 x 889). A graph's outputs depend
     on that graph only, so the oracle recomputes sampled graphs as a batch of their own."""
