@@ -587,6 +587,9 @@ __global__ void __launch_bounds__(256) k_edge_elem(EdgeElemArgs p) {
   constexpr int NV = MODE == EE_GZ1 ? 1 + KMAX : 2;   // column sums kept per column
   __shared__ __align__(16) unsigned short tile[32 * EE_PITCH];
   __shared__ float csum[4][NV][128];
+  // the attributes of the tile's 32 rows (several attributes: every lane of a wavefront needs the same values, so
+  // they are fetched once per tile and read back as LDS broadcasts)
+  __shared__ __align__(16) float attr_s[KMAX > 1 && MODE != EE_GZ2 ? 32 * KMAX : 4];
   const int tid = threadIdx.x, x = tid & 63;
   const int q = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int slab = blockIdx.x;
@@ -610,6 +613,15 @@ __global__ void __launch_bounds__(256) k_edge_elem(EdgeElemArgs p) {
   for (int j = 0; j < KMAX; ++j) { s10[j] = 0.f; s11[j] = 0.f; }
   for (int rb = blockIdx.y; rb < p.nrb; rb += gridDim.y) {
     const int rb16 = 2 * rb + hh;
+    if (KMAX > 1 && MODE != EE_GZ2) {
+      // (the previous tile's arithmetic lies before its two barriers, so the buffer is free)
+      for (int t = tid; t < 32 * KMAX; t += 256) {
+        const long r = (long)rb * 32 + t / KMAX;
+        const int j = t % KMAX;
+        attr_s[t] = r < p.E && j < p.k ? p.attr[r * p.k + j] : 0.f;
+      }
+      __syncthreads();
+    }
     // the two columns are neighbouring 16-byte slots of one half fragment
     const long tfrag = ((long)rb16 * ncb + (c >> 5)) * 1024 + (g * 32 + (c & 31)) * 16;
     u32x4_t in0, in1;
@@ -623,14 +635,12 @@ __global__ void __launch_bounds__(256) k_edge_elem(EdgeElemArgs p) {
     }
     unsigned ga[8], gb[8];
     float sc[8];
-    long rrow[8];
     bool ok[8];
 #pragma unroll
     for (int u = 0; u < 8; ++u) {
       const long r = tset_row(rb16, g, u);     // the same for all lanes of the wavefront
       ok[u] = r < p.E;
       const long rr = ok[u] ? r : lastrow;
-      rrow[u] = rr;
       const long di = p.dst[rr];
       if (MODE == EE_GZ2) {
         sc[u] = p.cvec[rr];
@@ -663,8 +673,9 @@ __global__ void __launch_bounds__(256) k_edge_elem(EdgeElemArgs p) {
         if (KMAX == 1) {
           at[0] = sc[u];
         } else {
+          const int lr = 16 * hh + 8 * (u >> 2) + 4 * g + (u & 3);   // row inside the tile
 #pragma unroll
-          for (int j = 0; j < KMAX; ++j) at[j] = j < p.k ? p.attr[rrow[u] * p.k + j] : 0.f;
+          for (int j = 0; j < KMAX; ++j) at[j] = attr_s[lr * KMAX + j];
         }
         float z0 = bf_lo(ga[u]) + bf_lo(gb[u]), z1 = bf_hi(ga[u]) + bf_hi(gb[u]);
 #pragma unroll
@@ -687,6 +698,9 @@ __global__ void __launch_bounds__(256) k_edge_elem(EdgeElemArgs p) {
           o0[u] = gz0; o1[u] = gz1;
         }
       }
+      // (several attributes: keep the rows apart, or the scheduler fetches the attributes of all eight rows first
+      // and the kernel runs out of registers)
+      if (KMAX > 1) __builtin_amdgcn_sched_barrier(0);
     }
     if (MODE != EE_GZ1) {   // g_z1 is only read row by row: it goes out row-major below
       u32x4_t t0, t1;
