@@ -25,6 +25,9 @@ from .model import (  # noqa: F401
     embed_fwd,
     embed_bwd,
     edge_rbf,
+    edge_rbf_bwd,
+    edge_geometry,
+    edge_geometry_bwd,
     mp_layer_fwd,
     mp_layer_bwd,
     pool_fwd,
@@ -37,4 +40,5 @@ from .model import (  # noqa: F401
     heads_deep_fwd,
     heads_deep_bwd,
     step_fwd_bwd,
+    conservative_forces,
 )

@@ -99,8 +99,47 @@ def edge_rbf(d2, k, rc):
     d = np.sqrt(np.asarray(d2, dtype=np.float64))
     mu = np.arange(k, dtype=np.float64) * (rc / (k - 1))
     gamma = ((k - 1) / rc) ** 2
-    fc = 0.5 * (np.cos(np.pi * d / rc) + 1.0)
+    fc = np.where(d < rc, 0.5 * (np.cos(np.pi * d / rc) + 1.0), 0.0)   # zero from the cutoff on (moved atoms)
     return np.exp(-gamma * (d[:, None] - mu[None, :]) ** 2) * fc[:, None]
+
+
+def edge_rbf_bwd(d2, k, rc, g_attr):
+    """g_d2[e] = sum_j g_attr[e, j] * d attr[e, j] / d d2_e, with d/d d2 = (1 / 2d) d/dd and
+    d attr_j / dd = exp(-gamma (d - mu_j)^2) * (-2 gamma (d - mu_j) fc(d) + fc'(d)),
+    fc'(d) = -(pi / 2 rc) sin(pi d / rc) inside the cutoff, 0 from the cutoff on.  d > 0 (distinct atoms)."""
+    assert k >= 2
+    d = np.sqrt(np.asarray(d2, dtype=np.float64))
+    mu = np.arange(k, dtype=np.float64) * (rc / (k - 1))
+    gamma = ((k - 1) / rc) ** 2
+    inside = d < rc
+    fc = np.where(inside, 0.5 * (np.cos(np.pi * d / rc) + 1.0), 0.0)
+    dfc = np.where(inside, -(np.pi / (2.0 * rc)) * np.sin(np.pi * d / rc), 0.0)
+    diff = d[:, None] - mu[None, :]
+    dattr_dd = np.exp(-gamma * diff ** 2) * (-2.0 * gamma * diff * fc[:, None] + dfc[:, None])
+    return np.sum(np.asarray(g_attr, dtype=np.float64) * dattr_dd, axis=1) / (2.0 * d)
+
+
+# ---------------------------------------------------------------------------------------------
+# edge geometry when the atoms move between layers (the E(n)-GNN coordinate update): the equivariant channel v is
+# the displacement of every atom from its input position, x_i = x0_i + v_i, the neighbour list (with its periodic
+# images) stays that of the input positions
+# ---------------------------------------------------------------------------------------------
+def edge_geometry(rvec0, v, dst, col):
+    """rvec_e = rvec0_e + v[dst_e] - v[col_e] (rvec0: destination minus source image at the input positions),
+    d2_e = |rvec_e|^2."""
+    v = np.asarray(v, dtype=np.float64)
+    rvec = np.asarray(rvec0, dtype=np.float64) + v[dst] - v[col]
+    return rvec, np.sum(rvec * rvec, axis=1)
+
+
+def edge_geometry_bwd(rvec, g_rvec, g_d2, dst, col, N):
+    """Reverse of edge_geometry. Returns (g_r [E,3] = g_rvec + 2 g_d2 rvec, the gradient with respect to the edge
+    vector through both of its uses; g_v [N,3] = sum over edges into i of g_r - sum over edges out of i of g_r)."""
+    g_r = np.asarray(g_rvec, dtype=np.float64) + 2.0 * np.asarray(g_d2, dtype=np.float64)[:, None] * rvec
+    g_v = np.zeros((N, 3), dtype=np.float64)
+    np.add.at(g_v, dst, g_r)
+    np.add.at(g_v, col, -g_r)
+    return g_r, g_v
 
 
 # ---------------------------------------------------------------------------------------------
@@ -134,13 +173,14 @@ def mp_layer_fwd(h, v, dst, col, d2, rvec, Wflat, alpha, attr=None):
     u = silu(z3)
     h_out = h + u @ W["W4"] + W["b4"]
     cache = dict(h=h, dst=np.asarray(dst), col=np.asarray(col), d2=d2, rvec=rvec, W=W, alpha=alpha,
-                 xin=xin, z1=z1, a1=a1, z2=z2, m=m, M=M, nin=nin, z3=z3, u=u)
+                 xin=xin, z1=z1, a1=a1, z2=z2, m=m, x=x, M=M, nin=nin, z3=z3, u=u)
     return h_out, v_out, cache
 
 
-def mp_layer_bwd(cache, g_hout, g_vout):
-    """Reverse mode of mp_layer_fwd. Returns (g_h, g_v, dict of weight gradients).
-    d2 and rvec are constants of the step: no gradient flows to positions."""
+def mp_layer_bwd(cache, g_hout, g_vout, edge_grads=False):
+    """Reverse mode of mp_layer_fwd. Returns (g_h, g_v, dict of weight gradients); with edge_grads also
+    g_attr [E,k] (gradient with respect to the edge attributes, d2 when the layer took none) and g_rvec [E,3]
+    (gradient with respect to the edge vectors through the update of v), from which position gradients follow."""
     c = cache
     W, alpha = c["W"], c["alpha"]
     dst, col, rvec = c["dst"], c["col"], c["rvec"]
@@ -173,6 +213,9 @@ def mp_layer_bwd(cache, g_hout, g_vout):
     g_xin = g_z1 @ W["W1"].T                                             # [E, 2H+1]
     np.add.at(g_h, dst, g_xin[:, :H])
     np.add.at(g_h, col, g_xin[:, H:2 * H])
+    if edge_grads:
+        g_rvec = alpha * c["x"][:, None] * g_vout[dst]
+        return g_h, g_v, gW, g_xin[:, 2 * H:], g_rvec
     return g_h, g_v, gW
 
 
@@ -396,19 +439,31 @@ def heads_deep_bwd(cache, g_energy, g_force):
 # whole step
 # ---------------------------------------------------------------------------------------------
 def step_fwd_bwd(Z, graph_off, source_id, graph, emb, layer_weights, head_weights, Hh, S, alpha,
-                 g_energy=None, g_force=None, keep_layers=False, D=None, attr=None):
+                 g_energy=None, g_force=None, keep_layers=False, D=None, attr=None, move=False, rbf=None,
+                 pos_grad=False):
     """Embedding -> L layers -> mean pool -> heads, then (if upstream gradients are given) the
     whole reverse pass. `graph` is the dict returned by oracle.radius_graph. D: hidden layers per
-    head (None: the one-hidden-layer heads of heads_fwd). attr [E,k]: edge attributes in place of d2."""
+    head (None: the one-hidden-layer heads of heads_fwd). attr [E,k]: edge attributes in place of d2.
+    rbf = (k, rc): the attributes are the radial basis of the current edge length (recomputed per layer when the
+    atoms move). move: the atoms move between layers, x = x0 + v, edge vectors and lengths are recomputed before
+    every layer. pos_grad (implied by move): the reverse pass also returns g_pos [N,3], the gradient with respect to
+    the input positions through every edge vector and edge length."""
     H = emb.shape[1]
     N = len(Z)
-    dst, col, d2, rvec = graph["dst"], graph["col"], graph["d2"], graph["rvec"]
+    dst, col, d2_0, rvec0 = graph["dst"], graph["col"], graph["d2"], graph["rvec"]
+    pos_grad = pos_grad or move
     h = embed_fwd(Z, emb)
     v = np.zeros((N, 3), dtype=np.float64)
-    caches, hs = [], [h]
+    caches, hs, geoms = [], [h], []
     for Wl in layer_weights:
-        h, v, c = mp_layer_fwd(h, v, dst, col, d2, rvec, Wl, alpha, attr=attr)
+        if move:
+            rvec, d2 = edge_geometry(rvec0, v, dst, col)
+        else:
+            rvec, d2 = np.asarray(rvec0, dtype=np.float64), np.asarray(d2_0, dtype=np.float64)
+        a = edge_rbf(d2, rbf[0], rbf[1]) if rbf is not None else attr
+        h, v, c = mp_layer_fwd(h, v, dst, col, d2, rvec, Wl, alpha, attr=a)
         caches.append(c)
+        geoms.append((rvec, d2))
         if keep_layers:
             hs.append(h)
     p = pool_fwd(h, graph_off)
@@ -426,8 +481,21 @@ def step_fwd_bwd(Z, graph_off, source_id, graph, emb, layer_weights, head_weight
         g_p, g_h, g_v, g_heads = heads_deep_bwd(hc, g_energy, g_force)
     g_h = g_h + pool_bwd(g_p, graph_off, N)
     g_layers = []
-    for c in reversed(caches):
-        g_h, g_v, gW = mp_layer_bwd(c, g_h, g_v)
+    g_r0 = np.zeros((len(dst), 3), dtype=np.float64)
+    for c, (rvec, d2) in zip(reversed(caches), reversed(geoms)):
+        if not pos_grad:
+            g_h, g_v, gW = mp_layer_bwd(c, g_h, g_v)
+        else:
+            g_h, g_v, gW, g_attr, g_rvec = mp_layer_bwd(c, g_h, g_v, edge_grads=True)
+            if rbf is not None:
+                g_d2 = edge_rbf_bwd(d2, rbf[0], rbf[1], g_attr)
+            else:
+                assert attr is None, "position gradients need attributes that are a function of the edge length"
+                g_d2 = g_attr[:, 0]
+            g_r, g_v_geom = edge_geometry_bwd(rvec, g_rvec, g_d2, dst, col, N)
+            g_r0 += g_r
+            if move:
+                g_v = g_v + g_v_geom
         g_layers.append(pack_fields(gW, _LAYER_FIELDS))
     g_layers.reverse()
     out.update(
@@ -435,4 +503,19 @@ def step_fwd_bwd(Z, graph_off, source_id, graph, emb, layer_weights, head_weight
         g_heads=g_heads,
         g_h0=g_h, g_v0=g_v,
     )
+    if pos_grad:
+        # rvec0_e = x0[dst] - x0[col] - image shift: every layer's edge-vector gradient lands on the input positions
+        g_pos = np.zeros((N, 3), dtype=np.float64)
+        np.add.at(g_pos, dst, g_r0)
+        np.add.at(g_pos, col, -g_r0)
+        out["g_pos"] = g_pos
     return out
+
+
+def conservative_forces(Z, graph_off, source_id, graph, emb, layer_weights, head_weights, Hh, S, alpha, **kw):
+    """F_i = -d E_total / d x_i with E_total = sum over graphs of (atoms in the graph) x (energy per atom): the
+    reverse pass seeded with the atom counts on the energies and nothing on the force head."""
+    n_at = np.diff(np.asarray(graph_off)).astype(np.float64)
+    out = step_fwd_bwd(Z, graph_off, source_id, graph, emb, layer_weights, head_weights, Hh, S, alpha,
+                       g_energy=n_at, g_force=np.zeros((len(Z), 3)), pos_grad=True, **kw)
+    return out["energy"], -out["g_pos"]

@@ -698,3 +698,213 @@ def test_layer_with_k_attributes_backward_equals_torch_autograd_and_finite_diffe
 
     num = (loss(W + eps * d) - loss(W - eps * d)) / (2 * eps)
     assert abs(num - np.sum(flat * d)) <= 1e-6 * max(1.0, abs(num))
+
+
+# ---------------------------------------------------------------------------------------------
+# atoms that move between layers, gradients with respect to the positions, conservative forces
+# ---------------------------------------------------------------------------------------------
+def test_edge_rbf_is_zero_from_the_cutoff_on_and_its_derivative_matches_finite_differences():
+    k, rc = 6, 4.0
+    beyond = oracle.edge_rbf(np.array([rc * rc, (rc + 0.3) ** 2, (1.9 * rc) ** 2]), k, rc)
+    assert np.all(beyond == 0.0)
+    g = oracle.edge_rbf_bwd(np.array([(rc + 0.3) ** 2]), k, rc, np.ones((1, k)))
+    assert np.all(g == 0.0)
+    rng = np.random.default_rng(5)
+    d2 = rng.uniform(0.2, rc, size=40) ** 2
+    ga = rng.standard_normal((40, k))
+    got = oracle.edge_rbf_bwd(d2, k, rc, ga)
+    eps = 1e-6
+    num = np.sum(ga * (oracle.edge_rbf(d2 + eps, k, rc) - oracle.edge_rbf(d2 - eps, k, rc)), axis=1) / (2 * eps)
+    assert np.max(np.abs(got - num)) <= 1e-7 * max(1.0, np.max(np.abs(num)))
+    # at a centre mu_j the Gaussian is flat: only the envelope's slope is left, -(pi / 2 rc) sin(pi mu / rc) / (2 mu)
+    j = 2
+    mu = j * rc / (k - 1)
+    e = np.zeros((1, k)); e[0, j] = 1.0
+    want = -(math.pi / (2 * rc)) * math.sin(math.pi * mu / rc) / (2 * mu)
+    assert abs(oracle.edge_rbf_bwd(np.array([mu * mu]), k, rc, e)[0] - want) <= 1e-15
+
+
+def test_edge_geometry_and_its_reverse():
+    P = make_problem(seed=50, H=4, L=1)
+    g, b = P["g"], P["b"]
+    rng = np.random.default_rng(6)
+    v = 0.1 * rng.standard_normal((b.N, 3))
+    rvec, d2 = oracle.edge_geometry(g["rvec"], v, g["dst"], g["col"])
+    # zero displacement: the neighbour search's own vectors and lengths
+    r0, d0 = oracle.edge_geometry(g["rvec"], np.zeros((b.N, 3)), g["dst"], g["col"])
+    assert np.array_equal(r0, np.asarray(g["rvec"], dtype=np.float64))
+    assert np.max(np.abs(d0 - g["d2"])) <= 1e-5
+    # moving every atom of a graph by the same vector changes nothing; edge by edge with scalars
+    shift = rng.standard_normal(3)
+    r1, _ = oracle.edge_geometry(g["rvec"], v + shift, g["dst"], g["col"])
+    assert np.max(np.abs(r1 - rvec)) <= 1e-14
+    for e in range(0, g["E"], 7):
+        i, j = int(g["dst"][e]), int(g["col"][e])
+        for c in range(3):
+            assert abs(rvec[e, c] - (float(g["rvec"][e, c]) + v[i, c] - v[j, c])) <= 1e-15
+        assert abs(d2[e] - sum(rvec[e, c] ** 2 for c in range(3))) <= 1e-13
+    # reverse against a dense signed incidence matrix
+    g_rvec = rng.standard_normal((g["E"], 3))
+    g_d2 = rng.standard_normal(g["E"])
+    g_r, g_v = oracle.edge_geometry_bwd(rvec, g_rvec, g_d2, g["dst"], g["col"], b.N)
+    B = np.zeros((b.N, g["E"]))
+    B[g["dst"], np.arange(g["E"])] += 1.0
+    B[g["col"], np.arange(g["E"])] -= 1.0          # a self-image edge (dst == col) cancels: its vector cannot change
+    assert np.max(np.abs(g_v - B @ g_r)) <= 1e-12
+    eps = 1e-6
+    dv = rng.standard_normal((b.N, 3))
+    f = lambda vv: (lambda r, q: float(np.sum(r * g_rvec) + np.sum(q * g_d2)))(*oracle.edge_geometry(g["rvec"], vv, g["dst"], g["col"]))
+    num = (f(v + eps * dv) - f(v - eps * dv)) / (2 * eps)
+    assert abs(num - np.sum(g_v * dv)) <= 1e-7 * max(1.0, abs(num))
+
+
+def _moved_graph(g, delta):
+    """The same neighbour list with every atom displaced by delta: edge vectors and lengths follow."""
+    r = np.asarray(g["rvec"], dtype=np.float64) + delta[g["dst"]] - delta[g["col"]]
+    out = dict(g)
+    out["rvec"], out["d2"] = r, np.sum(r * r, axis=1)
+    return out
+
+
+def _f64_graph(g):
+    return _moved_graph(g, np.zeros((int(max(g["dst"].max(), g["col"].max())) + 1, 3)))
+
+
+@pytest.mark.parametrize("move,rbf", [(False, None), (True, None), (False, (5, 4.0)), (True, (5, 4.0))])
+def test_position_gradient_by_finite_differences(move, rbf):
+    P = make_problem(seed=51, H=6, Hh=5, L=3, S=3)
+    b = P["b"]
+    rng = np.random.default_rng(8)
+    Ws = P["Ws"] if rbf is None else [init_layer_weights(rng, P["H"], k=rbf[0]).astype(np.float64) for _ in range(P["L"])]
+    g0 = _f64_graph(P["g"])     # lengths consistent with the vectors to the last bit
+
+    def step(g, grads):
+        return oracle.step_fwd_bwd(b.Z, b.graph_off, b.source_id, g, P["emb"], Ws, P["Wh"], P["Hh"], P["S"],
+                                   P["alpha"], P["gE"] if grads else None, P["gF"] if grads else None,
+                                   move=move, rbf=rbf, pos_grad=True)
+
+    out = step(g0, True)
+    delta = rng.standard_normal((b.N, 3))
+    eps = 1e-6
+    loss = lambda o: float(np.sum(P["gE"] * o["energy"]) + np.sum(P["gF"] * o["force"]))
+    num = (loss(step(_moved_graph(g0, eps * delta), False)) - loss(step(_moved_graph(g0, -eps * delta), False))) / (2 * eps)
+    ana = float(np.sum(out["g_pos"] * delta))
+    assert abs(num - ana) <= 1e-6 * max(1.0, abs(ana)), (num, ana)
+    # no net force on any structure (moving a whole structure changes no edge vector) ...
+    for gi in range(b.G):
+        lo, hi = int(b.graph_off[gi]), int(b.graph_off[gi + 1])
+        assert np.max(np.abs(out["g_pos"][lo:hi].sum(axis=0))) <= 1e-10 * max(1.0, np.max(np.abs(out["g_pos"])))
+    # ... and the weight gradients are those of the step without position gradients when nothing moves
+    if not move:
+        ref = oracle.step_fwd_bwd(b.Z, b.graph_off, b.source_id, g0, P["emb"], Ws, P["Wh"], P["Hh"], P["S"],
+                                  P["alpha"], P["gE"], P["gF"], rbf=rbf)
+        assert all(np.array_equal(a, c) for a, c in zip(ref["g_layers"], out["g_layers"]))
+
+
+def test_moving_atoms_weight_gradients_by_finite_differences_and_first_layer_equals_fixed_atoms():
+    P = make_problem(seed=52, H=6, Hh=5, L=3, S=3)
+    b = P["b"]
+    g0 = _f64_graph(P["g"])
+    rng = np.random.default_rng(9)
+
+    def step(Ws, grads, move=True):
+        return oracle.step_fwd_bwd(b.Z, b.graph_off, b.source_id, g0, P["emb"], Ws, P["Wh"], P["Hh"], P["S"],
+                                   P["alpha"], P["gE"] if grads else None, P["gF"] if grads else None,
+                                   move=move, keep_layers=True)
+
+    out = step(P["Ws"], True)
+    fixed = step(P["Ws"], False, move=False)
+    # before the first layer nothing has moved; afterwards the features differ
+    assert np.array_equal(out["hs"][1], fixed["hs"][1]) and not np.allclose(out["hs"][2], fixed["hs"][2])
+    d_Ws = [rng.standard_normal(w.shape) for w in P["Ws"]]
+    eps = 1e-6
+    loss = lambda o: float(np.sum(P["gE"] * o["energy"]) + np.sum(P["gF"] * o["force"]))
+    num = (loss(step([w + eps * d for w, d in zip(P["Ws"], d_Ws)], False))
+           - loss(step([w - eps * d for w, d in zip(P["Ws"], d_Ws)], False))) / (2 * eps)
+    ana = sum(float(np.sum(g * d)) for g, d in zip(out["g_layers"], d_Ws))
+    assert abs(num - ana) <= 1e-6 * max(1.0, abs(ana)), (num, ana)
+
+
+def test_moving_atoms_step_equals_torch_autograd():
+    P = make_problem(seed=53, H=5, Hh=4, L=2, S=3)
+    b, H, k, rc = P["b"], P["H"], 4, P["rc"]
+    rng = np.random.default_rng(10)
+    Ws = [init_layer_weights(rng, H, k=k).astype(np.float64) for _ in range(2)]
+    g0 = _f64_graph(P["g"])
+    out = oracle.step_fwd_bwd(b.Z, b.graph_off, b.source_id, g0, P["emb"], Ws, P["Wh"], P["Hh"], P["S"], P["alpha"],
+                              P["gE"], P["gF"], move=True, rbf=(k, rc))
+    # torch: positions as the differentiable leaf; edge vectors from positions and the image shifts of the list
+    dst = torch.as_tensor(g0["dst"], dtype=torch.long)
+    col = torch.as_tensor(g0["col"], dtype=torch.long)
+    x0 = torch.tensor(np.asarray(b.pos, dtype=np.float64), requires_grad=True)
+    t = torch.as_tensor(np.asarray(b.pos, dtype=np.float64)[g0["dst"]] - np.asarray(b.pos, dtype=np.float64)[g0["col"]]
+                        - g0["rvec"])                     # image shift of every edge (a constant)
+    tW = [torch.tensor(w, requires_grad=True) for w in Ws]
+    silu = torch.nn.functional.silu
+    h = torch.as_tensor(P["emb"])[torch.as_tensor(b.Z, dtype=torch.long)]
+    x = x0
+    sl = layer_field_slices(H, k)
+    mu = torch.arange(k, dtype=torch.float64) * (rc / (k - 1))
+    for w in tW:
+        f = {n: w[lo:hi].reshape(shp) for n, (lo, hi, shp) in sl.items()}
+        r = x[dst] - x[col] - t
+        d = torch.sqrt(torch.sum(r * r, 1))
+        fc = torch.where(d < rc, 0.5 * (torch.cos(math.pi * d / rc) + 1.0), torch.zeros_like(d))
+        attr = torch.exp(-((k - 1) / rc) ** 2 * (d[:, None] - mu[None, :]) ** 2) * fc[:, None]
+        m = silu(silu(torch.cat([h[dst], h[col], attr], 1) @ f["W1"] + f["b1"]) @ f["W2"] + f["b2"])
+        M = torch.zeros(b.N, H, dtype=torch.float64).index_add(0, dst, m) * P["alpha"]
+        x = x + P["alpha"] * torch.zeros(b.N, 3, dtype=torch.float64).index_add(0, dst, (m @ f["wx"])[:, None] * r)
+        h = h + silu(torch.cat([h, M], 1) @ f["W3"] + f["b3"]) @ f["W4"] + f["b4"]
+    assert np.max(np.abs((x - x0).detach().numpy() - out["v"])) <= 1e-12
+    assert np.max(np.abs(h.detach().numpy() - out["h"])) <= 1e-11
+    # the heads through the oracle's own reverse pass would be circular: seed the check at the layer outputs instead
+    gh = rng.standard_normal((b.N, H))
+    gv = rng.standard_normal((b.N, 3))
+    (torch.sum(h * torch.as_tensor(gh)) + torch.sum((x - x0) * torch.as_tensor(gv))).backward()
+    # oracle: the same seeds pushed through its layer / geometry reverse functions
+    N = b.N
+    vv = np.zeros((N, 3))
+    hh = oracle.embed_fwd(b.Z, P["emb"])
+    caches, geoms = [], []
+    for w in Ws:
+        rv, dd = oracle.edge_geometry(g0["rvec"], vv, g0["dst"], g0["col"])
+        hh, vv, c = oracle.mp_layer_fwd(hh, vv, g0["dst"], g0["col"], dd, rv, w, P["alpha"], attr=oracle.edge_rbf(dd, k, rc))
+        caches.append(c); geoms.append((rv, dd))
+    g_h, g_v, g_r0, gWs = gh, gv, 0.0, []
+    for c, (rv, dd) in zip(reversed(caches), reversed(geoms)):
+        g_h, g_v, gW, g_attr, g_rvec = oracle.mp_layer_bwd(c, g_h, g_v, edge_grads=True)
+        g_r, g_vg = oracle.edge_geometry_bwd(rv, g_rvec, oracle.edge_rbf_bwd(dd, k, rc, g_attr), g0["dst"], g0["col"], N)
+        g_v = g_v + g_vg
+        g_r0 = g_r0 + g_r
+        gWs.append(np.concatenate([np.ravel(gW[n]) for n in LAYER_FIELDS]))
+    gWs.reverse()
+    g_pos = np.zeros((N, 3))
+    np.add.at(g_pos, g0["dst"], g_r0)
+    np.add.at(g_pos, g0["col"], -g_r0)
+    # x - x0 does not depend on x0 directly, so torch's gradient at x0 is exactly the edge-vector path
+    assert np.max(np.abs(g_pos - x0.grad.numpy())) <= 1e-10 * max(1.0, np.max(np.abs(g_pos)))
+    for mine, ref in zip(gWs, tW):
+        assert np.max(np.abs(mine - ref.grad.numpy())) <= 1e-10 * max(1.0, np.max(np.abs(mine)))
+
+
+def test_conservative_forces_rotate_with_the_structure_and_match_energy_differences():
+    P = make_problem(seed=54, H=6, Hh=5, L=2, S=3)
+    b = P["b"]
+    g0 = _f64_graph(P["g"])
+    args = (b.Z, b.graph_off, b.source_id)
+    rest = (P["emb"], P["Ws"], P["Wh"], P["Hh"], P["S"], P["alpha"])
+    for move in (False, True):
+        e, F = oracle.conservative_forces(*args, g0, *rest, move=move)
+        # rotate every edge vector: energies stay, forces turn with the structure
+        Q = np.linalg.qr(np.random.default_rng(11).standard_normal((3, 3)))[0]
+        gq = dict(g0); gq["rvec"] = g0["rvec"] @ Q.T
+        eq, Fq = oracle.conservative_forces(*args, gq, *rest, move=move)
+        assert np.max(np.abs(eq - e)) <= 1e-12 and np.max(np.abs(Fq - F @ Q.T)) <= 1e-11 * max(1.0, np.max(np.abs(F)))
+        # one atom pushed along one axis: total energy changes by -F . dx
+        n_at = np.diff(b.graph_off)
+        i, c, eps = 3, 1, 1e-6
+        delta = np.zeros((b.N, 3)); delta[i, c] = eps
+        ep = oracle.step_fwd_bwd(*args, _moved_graph(g0, delta), *rest, move=move)["energy"]
+        em = oracle.step_fwd_bwd(*args, _moved_graph(g0, -delta), *rest, move=move)["energy"]
+        num = -float(np.sum(n_at * (ep - em))) / (2 * eps)
+        assert abs(num - F[i, c]) <= 1e-6 * max(1.0, abs(num)), (num, F[i, c])
