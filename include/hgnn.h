@@ -166,6 +166,9 @@ int32_t hgnn_mp_layer_bwd(void* stream, int32_t N, int64_t E, int32_t H, int32_t
  * 2 <= k <= 16 there; the layer takes 1 <= k <= 16 and any attributes. 1 <= H <= 1024, dtype HGNN_BF16 only (HGNN_F32
  * -> UNIMPLEMENTED): at every width this variant runs through the fragment-GEMM kernels. Other arguments, side
  * stream, errors and aliasing rules as for hgnn_mp_layer_*. Only enqueue work.
+ * _bwd can also hand out what position gradients are made of (both optional, NULL = not wanted):
+ *   g_attr [E,k]  gradient with respect to the edge attributes, g_attr[e][j] = sum_c g_z1[e][c] W1[2H + j][c]
+ *   g_rvec [E,3]  gradient with respect to the edge vectors through v', g_rvec_e = alpha (wx . m_e) g_v_out[dst_e]
  * ------------------------------------------------------------------------------------------- */
 int32_t hgnn_edge_rbf(void* stream, int64_t E, const float* d2 /*[E]*/, int32_t k, float rc,
                       float* attr /*out [E,k]*/);
@@ -187,7 +190,39 @@ int32_t hgnn_mp_layer_attr_bwd(void* stream, int32_t N, int64_t E, int32_t H, in
                                const float* h_in, const float* W, const void* saved, size_t saved_bytes,
                                const float* g_h_out /*[N,H]*/, const float* g_v_out /*[N,3]*/,
                                float* g_h_in /*out [N,H]*/, float* g_v_in /*out [N,3]*/,
-                               float* gW /*out, layout of W*/, void* ws, size_t ws_bytes);
+                               float* gW /*out, layout of W*/, float* g_attr /*out [E,k] or NULL*/,
+                               float* g_rvec /*out [E,3] or NULL*/, void* ws, size_t ws_bytes);
+
+/* ---------------------------------------------------------------------------------------------
+ * Atoms that move between layers, and gradients with respect to positions. The paper's backbone is the E(n)-GNN
+ * (section "Numerical Results"), whose layers also update the coordinates: here the equivariant channel v is read as
+ * the displacement of every atom from its input position, x_i = x0_i + v_i. The neighbour list (and the periodic image
+ * of every edge) stays that of the input positions; before every layer
+ *   hgnn_edge_geometry_fwd:  rvec_e = rvec0_e + (v[dst_e] - v[col_e]),  d2_e = |rvec_e|^2
+ * gives the layer its edge vectors and lengths (v = 0: those of the neighbour search). In the reverse pass
+ *   hgnn_edge_rbf_bwd:       g_d2_e = sum_j g_attr[e][j] d attr_j / d d2   (basis of hgnn_edge_rbf; edges of length 0
+ *                            give inf / nan: distinct atoms never coincide)
+ *   hgnn_edge_geometry_bwd:  g_r_e = g_rvec_e + 2 g_d2_e rvec_e            (g_d2 NULL: g_r = g_rvec)
+ *                            g_r_sum_e += g_r_e                             (optional)
+ *                            g_v[i] += sum_{e: dst_e = i} g_r_e - sum_{e: col_e = i} g_r_e   (optional, fixed order)
+ * turn a layer's g_attr / g_rvec into the gradient with respect to the displacements that entered the layer (add it to
+ * the layer's g_v_in when the atoms move) and accumulate the gradient with respect to rvec0; one last call with
+ * g_rvec = that sum, g_d2 = NULL and a zeroed g_v gives the gradient with respect to the input positions. The negative
+ * of that gradient for dL/dE = atoms per graph, dL/dF = 0 is the conservative force -dE/dx.
+ * g_r may alias g_rvec; g_r_sum may alias neither. row_ptr / colT_ptr / permT as produced by hgnn_radius_graph_fill.
+ * float32 throughout. Only enqueue work.
+ * ------------------------------------------------------------------------------------------- */
+int32_t hgnn_edge_geometry_fwd(void* stream, int32_t N, int64_t E, const float* rvec0 /*[E,3]*/,
+                               const float* v /*[N,3]*/, const int32_t* dst, const int32_t* col,
+                               float* rvec /*out [E,3]*/, float* d2 /*out [E]*/);
+
+int32_t hgnn_edge_rbf_bwd(void* stream, int64_t E, const float* d2 /*[E]*/, int32_t k, float rc,
+                          const float* g_attr /*[E,k]*/, float* g_d2 /*out [E]*/);
+
+int32_t hgnn_edge_geometry_bwd(void* stream, int32_t N, int64_t E, const int32_t* row_ptr, const int32_t* colT_ptr,
+                               const int32_t* permT, const float* rvec /*[E,3]*/, const float* g_rvec /*[E,3]*/,
+                               const float* g_d2 /*[E] or NULL*/, float* g_r /*out [E,3]*/,
+                               float* g_r_sum /*in/out [E,3] or NULL*/, float* g_v /*in/out [N,3] or NULL*/);
 
 /* ---------------------------------------------------------------------------------------------
  * Pooling over the contiguous atoms of each graph: p_g = sum or mean of h_i (mean gives the

@@ -21,7 +21,8 @@ EXPORTS = [
     "hgnn_radius_graph_workspace_bytes", "hgnn_radius_graph_count", "hgnn_radius_graph_fill",
     "hgnn_embed_fwd", "hgnn_embed_bwd", "hgnn_embed_bwd_workspace_bytes",
     "hgnn_set_side_stream", "hgnn_mp_layer_workspace_bytes", "hgnn_mp_layer_fwd", "hgnn_mp_layer_bwd",
-    "hgnn_edge_rbf", "hgnn_mp_layer_attr_workspace_bytes", "hgnn_mp_layer_attr_fwd", "hgnn_mp_layer_attr_bwd",
+    "hgnn_edge_rbf", "hgnn_edge_rbf_bwd", "hgnn_edge_geometry_fwd", "hgnn_edge_geometry_bwd",
+    "hgnn_mp_layer_attr_workspace_bytes", "hgnn_mp_layer_attr_fwd", "hgnn_mp_layer_attr_bwd",
     "hgnn_pool_by_graph_fwd", "hgnn_pool_by_graph_bwd",
     "hgnn_multihead_plan_ints", "hgnn_multihead_plan",
     "hgnn_multihead_decode_workspace_bytes", "hgnn_multihead_decode_fwd", "hgnn_multihead_decode_bwd",
@@ -78,7 +79,10 @@ _mpa_ws = _sig("hgnn_mp_layer_attr_workspace_bytes", i32, i64, i32, i32, i32, C.
 _mpa_fwd = _sig("hgnn_mp_layer_attr_fwd", vp, i32, i64, i32, i32, i32, f32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
                 vp, sz, vp, sz)
 _mpa_bwd = _sig("hgnn_mp_layer_attr_bwd", vp, i32, i64, i32, i32, i32, f32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz,
-                vp, vp, vp, vp, vp, vp, sz)
+                vp, vp, vp, vp, vp, vp, vp, vp, sz)
+_rbf_bwd = _sig("hgnn_edge_rbf_bwd", vp, i64, vp, i32, f32, vp, vp)
+_geom_fwd = _sig("hgnn_edge_geometry_fwd", vp, i32, i64, vp, vp, vp, vp, vp, vp)
+_geom_bwd = _sig("hgnn_edge_geometry_bwd", vp, i32, i64, vp, vp, vp, vp, vp, vp, vp, vp, vp)
 _adamw = _sig("hgnn_adamw_step", vp, i64, vp, vp, vp, vp, i32, C.c_double, C.c_double, C.c_double, C.c_double,
               C.c_double)
 _pool_fwd = _sig("hgnn_pool_by_graph_fwd", vp, i32, i32, i32, i32, vp, vp, vp)
@@ -188,10 +192,23 @@ def mp_layer_attr_fwd(N, E, H, k, dtype, alpha, row_ptr, dst, col, attr, rvec, h
 
 
 def mp_layer_attr_bwd(N, E, H, k, dtype, alpha, row_ptr, dst, col, attr, rvec, colT_ptr, permT, h_in, W, saved,
-                      g_h_out, g_v_out, g_h_in, g_v_in, gW, ws):
+                      g_h_out, g_v_out, g_h_in, g_v_in, gW, ws, g_attr=None, g_rvec=None):
     _check(_mpa_bwd(_stream(), N, E, H, k, dtype, alpha, _p(row_ptr), _p(dst), _p(col), _p(attr), _p(rvec),
                     _p(colT_ptr), _p(permT), _p(h_in), _p(W), _p(saved), _nbytes(saved), _p(g_h_out), _p(g_v_out),
-                    _p(g_h_in), _p(g_v_in), _p(gW), _p(ws), _nbytes(ws)))
+                    _p(g_h_in), _p(g_v_in), _p(gW), _p(g_attr), _p(g_rvec), _p(ws), _nbytes(ws)))
+
+
+def edge_rbf_bwd(E, d2, k, rc, g_attr, g_d2):
+    _check(_rbf_bwd(_stream(), E, _p(d2), k, rc, _p(g_attr), _p(g_d2)))
+
+
+def edge_geometry_fwd(N, E, rvec0, v, dst, col, rvec, d2):
+    _check(_geom_fwd(_stream(), N, E, _p(rvec0), _p(v), _p(dst), _p(col), _p(rvec), _p(d2)))
+
+
+def edge_geometry_bwd(N, E, row_ptr, colT_ptr, permT, rvec, g_rvec, g_d2, g_r, g_r_sum, g_v):
+    _check(_geom_bwd(_stream(), N, E, _p(row_ptr), _p(colT_ptr), _p(permT), _p(rvec), _p(g_rvec), _p(g_d2), _p(g_r),
+                     _p(g_r_sum), _p(g_v)))
 
 
 def mp_layer_fwd(N, E, H, dtype, alpha, row_ptr, dst, col, d2, rvec, h_in, v_in, W, h_out, v_out, saved, ws):

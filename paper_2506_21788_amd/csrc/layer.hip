@@ -446,7 +446,8 @@ extern "C" int32_t hgnn_mp_layer_attr_bwd(void* stream, int32_t N, int64_t E, in
                                           const float* attr, const float* rvec, const int32_t* colT_ptr,
                                           const int32_t* permT, const float* h_in, const float* W, const void* saved,
                                           size_t saved_bytes, const float* g_h_out, const float* g_v_out, float* g_h_in,
-                                          float* g_v_in, float* gW, void* ws, size_t ws_bytes) {
+                                          float* g_v_in, float* gW, float* g_attr, float* g_rvec, void* ws,
+                                          size_t ws_bytes) {
   hipStream_t st = static_cast<hipStream_t>(stream);
   HGNN_TRY(check_attr_args(N, E, H, k, dtype));
   HGNN_REQUIRE(gW && W && ws, HGNN_ERR_NULLPTR, "mp_layer_attr_bwd: null pointer");
@@ -464,6 +465,7 @@ extern "C" int32_t hgnn_mp_layer_attr_bwd(void* stream, int32_t N, int64_t E, in
   a.row_ptr = row_ptr; a.dst = dst; a.col = col; a.attr = attr; a.k = k; a.rvec = rvec;
   a.colT_ptr = colT_ptr; a.permT = permT;
   a.h_in = h_in; a.W = W; a.g_h_out = g_h_out; a.g_v_out = g_v_out; a.g_h_in = g_h_in; a.g_v_in = g_v_in; a.gW = gW;
+  a.g_attr = g_attr; a.g_rvec = g_rvec;
   a.saved = const_cast<void*>(saved); a.ws = ws;
   return wide_layer_bwd(st, a);
 }

@@ -47,6 +47,8 @@ struct WideLayerArgs {
   float* g_h_in = nullptr;
   float* g_v_in = nullptr;
   float* gW = nullptr;
+  float* g_attr = nullptr;   // optional out [E, k]: gradient with respect to the edge attributes (d2 when attr is null)
+  float* g_rvec = nullptr;   // optional out [E, 3]: gradient with respect to the edge vectors (through v')
   void* saved = nullptr;
   void* ws = nullptr;
 };

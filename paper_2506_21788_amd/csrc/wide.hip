@@ -768,7 +768,7 @@ template <int NCB>
 __global__ void __launch_bounds__(256) k_seg_fwd_w(int N, const int32_t* __restrict__ row_ptr, const char* __restrict__ z2_T,
                                                    const float* __restrict__ rvec, const float* __restrict__ wx, int H,
                                                    float alpha, const float* __restrict__ v_in, float* __restrict__ M,
-                                                   float* __restrict__ v_out) {
+                                                   float* __restrict__ v_out, float* __restrict__ xe) {
   const int lane = threadIdx.x & 63, g = lane >> 5, x = lane & 31;
   const int i = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (i >= N) return;
@@ -807,6 +807,14 @@ __global__ void __launch_bounds__(256) k_seg_fwd_w(int N, const int32_t* __restr
       s[0] = fmaf(y[u], rv[u][0], s[0]);
       s[1] = fmaf(y[u], rv[u][1], s[1]);
       s[2] = fmaf(y[u], rv[u][2], s[2]);
+    }
+    // x_e = wx . m_e of every edge, kept for the reverse pass (gradient with respect to the edge vectors)
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      float t = y[u];
+#pragma unroll
+      for (int o = 16; o > 0; o >>= 1) t += __shfl_xor(t, o);
+      if (x == 0 && ok[u]) xe[tset_row(rb16, g, u)] = t;
     }
   }
 #pragma unroll
@@ -880,23 +888,80 @@ __global__ void __launch_bounds__(256) k_segsum_rows(int N, int Hp, const int32_
 }
 
 static int32_t launch_seg_fwd_w(hipStream_t st, int Hp, int N, const int32_t* row_ptr, const char* z2_T, const float* rvec,
-                                const float* wx, int H, float alpha, const float* v_in, float* M, float* v_out) {
+                                const float* wx, int H, float alpha, const float* v_in, float* M, float* v_out,
+                                float* xe) {
   if (N <= 0) return HGNN_OK;
   ProfScope ps(PT_SEG_FWD, st);
   const unsigned grid = (unsigned)((N + 3) / 4);
   switch (Hp / 32) {
-    case 4: k_seg_fwd_w<4><<<grid, 256, 0, st>>>(N, row_ptr, z2_T, rvec, wx, H, alpha, v_in, M, v_out); break;
-    case 8: k_seg_fwd_w<8><<<grid, 256, 0, st>>>(N, row_ptr, z2_T, rvec, wx, H, alpha, v_in, M, v_out); break;
-    case 12: k_seg_fwd_w<12><<<grid, 256, 0, st>>>(N, row_ptr, z2_T, rvec, wx, H, alpha, v_in, M, v_out); break;
-    case 16: k_seg_fwd_w<16><<<grid, 256, 0, st>>>(N, row_ptr, z2_T, rvec, wx, H, alpha, v_in, M, v_out); break;
-    case 20: k_seg_fwd_w<20><<<grid, 256, 0, st>>>(N, row_ptr, z2_T, rvec, wx, H, alpha, v_in, M, v_out); break;
-    case 24: k_seg_fwd_w<24><<<grid, 256, 0, st>>>(N, row_ptr, z2_T, rvec, wx, H, alpha, v_in, M, v_out); break;
-    case 28: k_seg_fwd_w<28><<<grid, 256, 0, st>>>(N, row_ptr, z2_T, rvec, wx, H, alpha, v_in, M, v_out); break;
-    case 32: k_seg_fwd_w<32><<<grid, 256, 0, st>>>(N, row_ptr, z2_T, rvec, wx, H, alpha, v_in, M, v_out); break;
+    case 4: k_seg_fwd_w<4><<<grid, 256, 0, st>>>(N, row_ptr, z2_T, rvec, wx, H, alpha, v_in, M, v_out, xe); break;
+    case 8: k_seg_fwd_w<8><<<grid, 256, 0, st>>>(N, row_ptr, z2_T, rvec, wx, H, alpha, v_in, M, v_out, xe); break;
+    case 12: k_seg_fwd_w<12><<<grid, 256, 0, st>>>(N, row_ptr, z2_T, rvec, wx, H, alpha, v_in, M, v_out, xe); break;
+    case 16: k_seg_fwd_w<16><<<grid, 256, 0, st>>>(N, row_ptr, z2_T, rvec, wx, H, alpha, v_in, M, v_out, xe); break;
+    case 20: k_seg_fwd_w<20><<<grid, 256, 0, st>>>(N, row_ptr, z2_T, rvec, wx, H, alpha, v_in, M, v_out, xe); break;
+    case 24: k_seg_fwd_w<24><<<grid, 256, 0, st>>>(N, row_ptr, z2_T, rvec, wx, H, alpha, v_in, M, v_out, xe); break;
+    case 28: k_seg_fwd_w<28><<<grid, 256, 0, st>>>(N, row_ptr, z2_T, rvec, wx, H, alpha, v_in, M, v_out, xe); break;
+    case 32: k_seg_fwd_w<32><<<grid, 256, 0, st>>>(N, row_ptr, z2_T, rvec, wx, H, alpha, v_in, M, v_out, xe); break;
     default: return set_error(HGNN_ERR_BAD_SHAPE, "padded width %d is not supported", Hp);
   }
   HGNN_LAUNCH_CHECK("k_seg_fwd_w");
   return HGNN_OK;
+}
+
+// g_attr[e][j] = sum_c g_z1[e][c] W1d[j][c], j < k <= 32: a product with one 32-column block of output. W1d^T sits in
+// LDS as B fragments (built once per workgroup), every wavefront multiplies 32-row blocks of the row-major bf16 g_z1,
+// whose 16-byte pieces are A fragments as they stand (lane (g, r): row r, columns 16 kb + 8 g ..).
+__global__ void __launch_bounds__(256) k_gattr(int64_t E, int nrb, int H, int Hp, int k,
+                                               const unsigned short* __restrict__ gz1, const float* __restrict__ w1d,
+                                               float* __restrict__ g_attr) {
+  extern __shared__ __align__(16) u32x4_t bfrag[];
+  const int lane = threadIdx.x & 63, g = lane >> 5, n = lane & 31;
+  const int wave = threadIdx.x >> 6;
+  const int nkb = Hp >> 4;
+  for (int kb = wave; kb < nkb; kb += 4) {
+    u32x4_t wv;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int c0 = 16 * kb + 8 * g + 2 * q;
+      const float f0 = (n < k && c0 < H) ? w1d[(long)n * H + c0] : 0.f;
+      const float f1 = (n < k && c0 + 1 < H) ? w1d[(long)n * H + c0 + 1] : 0.f;
+      wv[q] = pack_bf16x2(f0, f1);
+    }
+    bfrag[kb * 64 + lane] = wv;
+  }
+  __syncthreads();
+  for (int rb = blockIdx.x * 4 + wave; rb < nrb; rb += gridDim.x * 4) {
+    f32x16_t acc;
+#pragma unroll
+    for (int u = 0; u < 16; ++u) acc[u] = 0.f;
+    const char* base = reinterpret_cast<const char*>(gz1) + ((long)rb * 32 + n) * Hp * 2 + g * 16;
+    for (int kb0 = 0; kb0 < nkb; kb0 += 8) {   // Hp is a multiple of 128: eight loads in flight
+      u32x4_t av[8];
+#pragma unroll
+      for (int q = 0; q < 8; ++q) av[q] = *reinterpret_cast<const u32x4_t*>(base + (kb0 + q) * 32);
+#pragma unroll
+      for (int q = 0; q < 8; ++q)
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, av[q]),
+                                                      __builtin_bit_cast(bf16x8_t, bfrag[(kb0 + q) * 64 + lane]), acc, 0, 0, 0);
+    }
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+      const long row = (long)rb * 32 + 8 * (u >> 2) + 4 * g + (u & 3);
+      if (n < k && row < E) g_attr[row * k + n] = acc[u];
+    }
+  }
+}
+
+// g_rvec_e = alpha x_e g_v'[dst_e]   (v'_i = v_i + alpha sum x_e rvec_e)
+__global__ void k_edge_grvec(int64_t E, const int32_t* __restrict__ dst, const float* __restrict__ xe,
+                             const float* __restrict__ g_v, float alpha, float* __restrict__ g_rvec) {
+  const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= E) return;
+  const size_t i = (size_t)dst[e];
+  const float t = alpha * xe[e];
+  g_rvec[3 * e] = t * g_v[3 * i];
+  g_rvec[3 * e + 1] = t * g_v[3 * i + 1];
+  g_rvec[3 * e + 2] = t * g_v[3 * i + 2];
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -942,6 +1007,7 @@ struct WideSaved {
   float* z3;            // [Np, Hp]
   char* hM_T;           // [Np, 2 Hp] T fragments of [h ; M]     (operands of the reverse pass's weight gradients)
   char* a3_T;           // [Np, Hp] T fragments of silu(z3)
+  float* xe;            // [Ep] wx . m_e
   size_t bytes;
 };
 static WideSaved carve_saved_w(void* p, const WideDims& d) {
@@ -955,6 +1021,7 @@ static WideSaved carve_saved_w(void* p, const WideDims& d) {
   s.z3 = c.take<float>((size_t)d.Np * d.Hp);
   s.hM_T = c.take<char>(d.node_frag_bytes(2));
   s.a3_T = c.take<char>(d.node_frag_bytes(1));
+  s.xe = c.take<float>((size_t)d.Ep);
   s.bytes = c.used();
   return s;
 }
@@ -1162,7 +1229,7 @@ int32_t wide_layer_fwd(hipStream_t st, const WideLayerArgs& a) {
     g.bias = W + o.b2; g.nbias = H;
     HGNN_TRY(launch_fgemm_rows_T(st, g));
   }
-  HGNN_TRY(launch_seg_fwd_w(st, Hp, d.N, a.row_ptr, s.z2_T, a.rvec, W + o.wx, H, a.alpha, a.v_in, s.M, a.v_out));
+  HGNN_TRY(launch_seg_fwd_w(st, Hp, d.N, a.row_ptr, s.z2_T, a.rvec, W + o.wx, H, a.alpha, a.v_in, s.M, a.v_out, s.xe));
   {  // M -> second half of the [h ; M] operand
     ToFragArgs t;
     t.X = s.M; t.ldx = Hp; t.M = d.N; t.Mp = d.Np; t.ncol = Hp; t.Cp = Hp;
@@ -1293,6 +1360,17 @@ int32_t wide_layer_bwd(hipStream_t st, const WideLayerArgs& a) {
     if (k == 1) k_edge_elem<EE_GZ1, 1><<<egrid, 256, 0, st>>>(e);
     else k_edge_elem<EE_GZ1, 16><<<egrid, 256, 0, st>>>(e);
     HGNN_LAUNCH_CHECK("k_edge_elem (g_z1)");
+  }
+  if (a.g_attr && d.E > 0) {  // gradient with respect to the edge attributes: g_z1 W1d^T
+    ProfScope ps(PT_EDGE_ELEM, st);
+    const int nwg = std::min(e.nrb / 4, 512);   // Ep is a multiple of 256: nrb / 4 >= 2
+    k_gattr<<<nwg, 256, (size_t)(Hp / 16) * 1024, st>>>(d.E, e.nrb, H, Hp, k, e.gz1_rm, e.w1d, a.g_attr);
+    HGNN_LAUNCH_CHECK("k_gattr");
+  }
+  if (a.g_rvec && d.E > 0) {
+    ProfScope ps(PT_MISC, st);
+    k_edge_grvec<<<(unsigned)((d.E + 255) / 256), 256, 0, st>>>(d.E, a.dst, s.xe, a.g_v_out, a.alpha, a.g_rvec);
+    HGNN_LAUNCH_CHECK("k_edge_grvec");
   }
   // g_P, g_Q: per-atom sums of g_z1 over the destination-sorted and the source-sorted lists
   if (d.N > 0) {

@@ -64,9 +64,15 @@ class HotPath:
     forward and backward. Inputs are numpy arrays (uploaded once); outputs stay on the device."""
 
     def __init__(self, batch, rc, H, L, S, dtype, emb, layer_weights, head_weights, alpha=None, Hh=None, D=None,
-                 rbf_k=None):
+                 rbf_k=None, move=False, pos_grad=False):
         """D: hidden layers per head (the deep-head entry points); None: the one-hidden-layer heads.
-        rbf_k: number of radial-basis edge attributes that take the place of d2 (None: d2 itself)."""
+        rbf_k: number of radial-basis edge attributes that take the place of d2 (None: d2 itself).
+        move: the atoms move between layers (x = x0 + v): edge vectors, lengths and attributes are recomputed
+        before every layer. pos_grad (implied by move): backward() also leaves the gradient with respect to the input
+        positions in g_pos. Both run the layers through the edge-attribute entry points (bf16 operands)."""
+        self.move = bool(move)
+        self.pos_grad = bool(pos_grad or move)
+        self.k = rbf_k if rbf_k is not None else (1 if self.pos_grad else None)   # None: the plain layer calls
         self.N, self.G, self.H, self.L, self.S = batch.N, batch.G, H, L, S
         self.Hh = H if Hh is None else Hh
         self.D = D
@@ -101,11 +107,23 @@ class HotPath:
             return
         N, G, H, L, S = self.N, self.G, self.H, self.L, self.S
         f32 = dict(dtype=torch.float32, device="cuda")
-        if self.rbf_k is None:
+        if self.k is None:
             ws_b, saved_b = B.mp_layer_workspace_bytes(N, E, H, self.dtype)
         else:
-            ws_b, saved_b = B.mp_layer_attr_workspace_bytes(N, E, H, self.rbf_k, self.dtype)
-            self.attr = torch.empty((max(E, 1), self.rbf_k), **f32)
+            ws_b, saved_b = B.mp_layer_attr_workspace_bytes(N, E, H, self.k, self.dtype)
+            En = max(E, 1)
+            nl = L if self.move else 1            # per-layer geometry only when the atoms move
+            if self.move:
+                self.rvec_l = [torch.empty((En, 3), **f32) for _ in range(L)]
+                self.d2_l = [torch.empty(En, **f32) for _ in range(L)]
+            if self.rbf_k is not None:
+                self.attr_l = [torch.empty((En, self.k), **f32) for _ in range(nl)]
+            if self.pos_grad:
+                self.g_attr = torch.empty((En, self.k), **f32)
+                self.g_d2 = torch.empty(En, **f32)
+                self.g_rvec = torch.empty((En, 3), **f32)
+                self.g_r0 = torch.empty((En, 3), **f32)
+                self.g_pos = torch.empty((N, 3), **f32)
         if self.D is None:
             hws_b, hsaved_b = B.multihead_decode_workspace_bytes(N, G, H, self.Hh, S, self.dtype)
         else:
@@ -130,16 +148,18 @@ class HotPath:
     def forward(self):
         g, N, G, H = self.graph, self.N, self.G, self.H
         B.embed_fwd(N, H, self.Z, self.emb, self.h[0])
-        if self.rbf_k is not None:
-            B.edge_rbf(g.E, g.d2, self.rbf_k, self.rc, self.attr)
         for l in range(self.L):
-            if self.rbf_k is None:
+            if self.k is None:
                 B.mp_layer_fwd(N, g.E, H, self.dtype, self.alpha, g.row_ptr, g.dst, g.col, g.d2, g.rvec,
                                self.h[l], self.v[l], self.W[l], self.h[l + 1], self.v[l + 1], self.saved[l], self.ws)
-            else:
-                B.mp_layer_attr_fwd(N, g.E, H, self.rbf_k, self.dtype, self.alpha, g.row_ptr, g.dst, g.col, self.attr,
-                                    g.rvec, self.h[l], self.v[l], self.W[l], self.h[l + 1], self.v[l + 1],
-                                    self.saved[l], self.ws)
+                continue
+            if self.move:
+                B.edge_geometry_fwd(N, g.E, g.rvec, self.v[l], g.dst, g.col, self.rvec_l[l], self.d2_l[l])
+            if self.rbf_k is not None and (self.move or l == 0):
+                B.edge_rbf(g.E, self._d2(l), self.k, self.rc, self.attr_l[l])
+            B.mp_layer_attr_fwd(N, g.E, H, self.k, self.dtype, self.alpha, g.row_ptr, g.dst, g.col, self._attr(l),
+                                self._rvec(l), self.h[l], self.v[l], self.W[l], self.h[l + 1], self.v[l + 1],
+                                self.saved[l], self.ws)
         B.pool_by_graph_fwd(N, G, H, B.POOL_MEAN, self.graph_off, self.h[-1], self.p)
         if self.D is None:
             B.multihead_decode_fwd(N, G, H, self.Hh, self.S, self.dtype, self.plan, self.p, self.h[-1], self.v[-1],
@@ -147,6 +167,18 @@ class HotPath:
         else:
             B.multihead_deep_fwd(N, G, H, self.Hh, self.D, self.S, self.dtype, self.plan, self.p, self.h[-1],
                                  self.v[-1], self.Whead, self.energy, self.force, self.hsaved, self.ws)
+
+    # geometry and attributes of layer l (those of the neighbour search unless the atoms move)
+    def _rvec(self, l):
+        return self.rvec_l[l] if self.move else self.graph.rvec
+
+    def _d2(self, l):
+        return self.d2_l[l] if self.move else self.graph.d2
+
+    def _attr(self, l):
+        if self.rbf_k is None:
+            return self._d2(l)                       # one attribute per edge: the squared length, [E] = [E,1]
+        return self.attr_l[l if self.move else 0]
 
     def backward(self, g_energy, g_force):
         g, N, G, H = self.graph, self.N, self.G, self.H
@@ -161,15 +193,31 @@ class HotPath:
         B.pool_by_graph_bwd(N, G, H, B.POOL_MEAN, self.graph_off, self.g_p, self.g_h[0], True)
         cur = 0
         for l in reversed(range(self.L)):
-            if self.rbf_k is None:
+            if self.k is None:
                 B.mp_layer_bwd(N, g.E, H, self.dtype, self.alpha, g.row_ptr, g.dst, g.col, g.d2, g.rvec, g.colT_ptr,
                                g.permT, self.h[l], self.W[l], self.saved[l], self.g_h[cur], self.g_v[cur],
                                self.g_h[1 - cur], self.g_v[1 - cur], self.gW[l], self.ws)
             else:
-                B.mp_layer_attr_bwd(N, g.E, H, self.rbf_k, self.dtype, self.alpha, g.row_ptr, g.dst, g.col, self.attr,
-                                    g.rvec, g.colT_ptr, g.permT, self.h[l], self.W[l], self.saved[l], self.g_h[cur],
-                                    self.g_v[cur], self.g_h[1 - cur], self.g_v[1 - cur], self.gW[l], self.ws)
+                pg = self.pos_grad
+                B.mp_layer_attr_bwd(N, g.E, H, self.k, self.dtype, self.alpha, g.row_ptr, g.dst, g.col, self._attr(l),
+                                    self._rvec(l), g.colT_ptr, g.permT, self.h[l], self.W[l], self.saved[l],
+                                    self.g_h[cur], self.g_v[cur], self.g_h[1 - cur], self.g_v[1 - cur], self.gW[l],
+                                    self.ws, g_attr=self.g_attr if pg else None, g_rvec=self.g_rvec if pg else None)
+                if pg:
+                    if l == self.L - 1:
+                        self.g_r0.zero_()
+                    if self.rbf_k is not None:
+                        B.edge_rbf_bwd(g.E, self._d2(l), self.k, self.rc, self.g_attr, self.g_d2)
+                    g_d2 = self.g_d2 if self.rbf_k is not None else self.g_attr   # k = 1: the attribute is d2
+                    B.edge_geometry_bwd(N, g.E, g.row_ptr, g.colT_ptr, g.permT, self._rvec(l), self.g_rvec, g_d2,
+                                        self.g_rvec, self.g_r0, self.g_v[1 - cur] if self.move else None)
             cur = 1 - cur
+        if self.pos_grad:
+            # rvec0 = x0[dst] - x0[col] - image shift: the summed edge-vector gradients land on the input positions
+            self.g_pos.zero_()
+            if self.L > 0:
+                B.edge_geometry_bwd(N, g.E, g.row_ptr, g.colT_ptr, g.permT, None, self.g_r0, None, self.g_rvec, None,
+                                    self.g_pos)
         B.embed_bwd(N, H, self.Z, self.g_h[cur], self.g_emb, self.ws)
         self.g_h0, self.g_v0 = self.g_h[cur], self.g_v[cur]
 

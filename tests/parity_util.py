@@ -47,11 +47,14 @@ def problem_from_config(name, rbf_k=None, **over):
     return dict(batch=batch, hp=hp, emb=emb, Ws=Ws, Wh=Wh, gE=gE, gF=gF)
 
 
-def problem_from_batch(batch, rc, H, L, S, dtype, seed=0, Hh=None, D=None, rbf_k=None):
+def problem_from_batch(batch, rc, H, L, S, dtype, seed=0, Hh=None, D=None, rbf_k=None, move=False, pos_grad=False):
+    """move: the atoms move between layers; pos_grad: the reverse pass also gives the position gradient."""
     emb, Ws, Wh, gE, gF = make_weights(seed, H, L, S, batch.N, batch.G, Hh, D, rbf_k or 1)
     hp = dict(rc=rc, H=H, L=L, S=S, dtype=dtype, seed=seed, name="custom")
     if rbf_k:
         hp["rbf_k"] = rbf_k
+    if move or pos_grad:
+        hp.update(move=bool(move), pos_grad=True)
     if D is not None:
         hp.update(Hh=Hh, D=D)
     return dict(batch=batch, hp=hp, emb=emb, Ws=Ws, Wh=Wh, gE=gE, gF=gF)
@@ -64,20 +67,23 @@ def oracle_graph(P):
 
 def oracle_step(P, graph, alpha, grads=True, keep_layers=False):
     b, hp = P["batch"], P["hp"]
-    attr = oracle.edge_rbf(graph["d2"], hp["rbf_k"], hp["rc"]) if hp.get("rbf_k") else None
+    geom = hp.get("pos_grad", False)
+    rbf = (hp["rbf_k"], hp["rc"]) if hp.get("rbf_k") and geom else None
+    attr = oracle.edge_rbf(graph["d2"], hp["rbf_k"], hp["rc"]) if hp.get("rbf_k") and not geom else None
     return oracle.step_fwd_bwd(b.Z, b.graph_off, b.source_id, graph, P["emb"].astype(np.float64),
                                [w.astype(np.float64) for w in P["Ws"]], P["Wh"].astype(np.float64),
                                hp.get("Hh", hp["H"]), hp["S"], alpha,
                                P["gE"].astype(np.float64) if grads else None,
                                P["gF"].astype(np.float64) if grads else None, keep_layers=keep_layers, D=hp.get("D"),
-                               attr=attr)
+                               attr=attr, rbf=rbf, move=hp.get("move", False), pos_grad=geom)
 
 
 def gpu_hotpath(P, alpha=None):
     from paper_2506_21788_amd.step import HotPath
     b, hp = P["batch"], P["hp"]
     return HotPath(b, hp["rc"], hp["H"], hp["L"], hp["S"], hp["dtype"], P["emb"], P["Ws"], P["Wh"], alpha=alpha,
-                   Hh=hp.get("Hh"), D=hp.get("D"), rbf_k=hp.get("rbf_k"))
+                   Hh=hp.get("Hh"), D=hp.get("D"), rbf_k=hp.get("rbf_k"), move=hp.get("move", False),
+                   pos_grad=hp.get("pos_grad", False))
 
 
 def assert_graph_equal(got, want):
