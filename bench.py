@@ -158,6 +158,10 @@ def main():
                     help="also time forward + backward replayed as one HIP graph (graph prebuilt)")
     ap.add_argument("--rbf", type=int, default=0, metavar="K",
                     help="K radial-basis edge attributes in place of d2 (2..16; every layer then runs on the fragment path)")
+    ap.add_argument("--pos-grad", action="store_true",
+                    help="the reverse pass also gives the gradient with respect to positions (fragment path, bf16)")
+    ap.add_argument("--move", action="store_true",
+                    help="the atoms move between layers (edge geometry recomputed per layer; implies --pos-grad)")
     ap.add_argument("--calib-copy", action="store_true", help="only run a 1 GiB copy kernel (counter calibration)")
     ap.add_argument("--calib-mfma", action="store_true", help="only run the matrix-core rate probe")
     args = ap.parse_args()
@@ -177,7 +181,7 @@ def main():
     from paper_2506_21788_amd import binding as B
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
-    P = problem_from_config(args.config, rbf_k=args.rbf or None)
+    P = problem_from_config(args.config, rbf_k=args.rbf or None, move=args.move, pos_grad=args.pos_grad)
     b, hp = P["batch"], P["hp"]
     hot = gpu_hotpath(P)
     gE = torch.as_tensor(P["gE"]).cuda()
@@ -265,7 +269,8 @@ def main():
         "value": E / t_full, "unit": "edges/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": t_full * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": hp["dtype"], "data": "synthetic",
-        "config": {"workload": f"{args.config}: {hp['desc']}" + (f" + {args.rbf} radial-basis edge attributes" if args.rbf else ""),
+        "config": {"workload": f"{args.config}: {hp['desc']}" + (f" + {args.rbf} radial-basis edge attributes" if args.rbf else "")
+                   + (" + moving atoms" if args.move else "") + (" + position gradients" if args.move or args.pos_grad else ""),
                    "atoms": N, "graphs": G, "edges": E, "H": H,
                    "layers": L, "sources": hp["S"], "cutoff": hp["rc"], "alpha": hot.alpha,
                    "head_width": hp.get("Hh", H), "head_hidden_layers": hp.get("D", 1)},

@@ -768,7 +768,7 @@ template <int NCB>
 __global__ void __launch_bounds__(256) k_seg_fwd_w(int N, const int32_t* __restrict__ row_ptr, const char* __restrict__ z2_T,
                                                    const float* __restrict__ rvec, const float* __restrict__ wx, int H,
                                                    float alpha, const float* __restrict__ v_in, float* __restrict__ M,
-                                                   float* __restrict__ v_out, float* __restrict__ xe) {
+                                                   float* __restrict__ v_out) {
   const int lane = threadIdx.x & 63, g = lane >> 5, x = lane & 31;
   const int i = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (i >= N) return;
@@ -807,14 +807,6 @@ __global__ void __launch_bounds__(256) k_seg_fwd_w(int N, const int32_t* __restr
       s[0] = fmaf(y[u], rv[u][0], s[0]);
       s[1] = fmaf(y[u], rv[u][1], s[1]);
       s[2] = fmaf(y[u], rv[u][2], s[2]);
-    }
-    // x_e = wx . m_e of every edge, kept for the reverse pass (gradient with respect to the edge vectors)
-#pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      float t = y[u];
-#pragma unroll
-      for (int o = 16; o > 0; o >>= 1) t += __shfl_xor(t, o);
-      if (x == 0 && ok[u]) xe[tset_row(rb16, g, u)] = t;
     }
   }
 #pragma unroll
@@ -888,20 +880,19 @@ __global__ void __launch_bounds__(256) k_segsum_rows(int N, int Hp, const int32_
 }
 
 static int32_t launch_seg_fwd_w(hipStream_t st, int Hp, int N, const int32_t* row_ptr, const char* z2_T, const float* rvec,
-                                const float* wx, int H, float alpha, const float* v_in, float* M, float* v_out,
-                                float* xe) {
+                                const float* wx, int H, float alpha, const float* v_in, float* M, float* v_out) {
   if (N <= 0) return HGNN_OK;
   ProfScope ps(PT_SEG_FWD, st);
   const unsigned grid = (unsigned)((N + 3) / 4);
   switch (Hp / 32) {
-    case 4: k_seg_fwd_w<4><<<grid, 256, 0, st>>>(N, row_ptr, z2_T, rvec, wx, H, alpha, v_in, M, v_out, xe); break;
-    case 8: k_seg_fwd_w<8><<<grid, 256, 0, st>>>(N, row_ptr, z2_T, rvec, wx, H, alpha, v_in, M, v_out, xe); break;
-    case 12: k_seg_fwd_w<12><<<grid, 256, 0, st>>>(N, row_ptr, z2_T, rvec, wx, H, alpha, v_in, M, v_out, xe); break;
-    case 16: k_seg_fwd_w<16><<<grid, 256, 0, st>>>(N, row_ptr, z2_T, rvec, wx, H, alpha, v_in, M, v_out, xe); break;
-    case 20: k_seg_fwd_w<20><<<grid, 256, 0, st>>>(N, row_ptr, z2_T, rvec, wx, H, alpha, v_in, M, v_out, xe); break;
-    case 24: k_seg_fwd_w<24><<<grid, 256, 0, st>>>(N, row_ptr, z2_T, rvec, wx, H, alpha, v_in, M, v_out, xe); break;
-    case 28: k_seg_fwd_w<28><<<grid, 256, 0, st>>>(N, row_ptr, z2_T, rvec, wx, H, alpha, v_in, M, v_out, xe); break;
-    case 32: k_seg_fwd_w<32><<<grid, 256, 0, st>>>(N, row_ptr, z2_T, rvec, wx, H, alpha, v_in, M, v_out, xe); break;
+    case 4: k_seg_fwd_w<4><<<grid, 256, 0, st>>>(N, row_ptr, z2_T, rvec, wx, H, alpha, v_in, M, v_out); break;
+    case 8: k_seg_fwd_w<8><<<grid, 256, 0, st>>>(N, row_ptr, z2_T, rvec, wx, H, alpha, v_in, M, v_out); break;
+    case 12: k_seg_fwd_w<12><<<grid, 256, 0, st>>>(N, row_ptr, z2_T, rvec, wx, H, alpha, v_in, M, v_out); break;
+    case 16: k_seg_fwd_w<16><<<grid, 256, 0, st>>>(N, row_ptr, z2_T, rvec, wx, H, alpha, v_in, M, v_out); break;
+    case 20: k_seg_fwd_w<20><<<grid, 256, 0, st>>>(N, row_ptr, z2_T, rvec, wx, H, alpha, v_in, M, v_out); break;
+    case 24: k_seg_fwd_w<24><<<grid, 256, 0, st>>>(N, row_ptr, z2_T, rvec, wx, H, alpha, v_in, M, v_out); break;
+    case 28: k_seg_fwd_w<28><<<grid, 256, 0, st>>>(N, row_ptr, z2_T, rvec, wx, H, alpha, v_in, M, v_out); break;
+    case 32: k_seg_fwd_w<32><<<grid, 256, 0, st>>>(N, row_ptr, z2_T, rvec, wx, H, alpha, v_in, M, v_out); break;
     default: return set_error(HGNN_ERR_BAD_SHAPE, "padded width %d is not supported", Hp);
   }
   HGNN_LAUNCH_CHECK("k_seg_fwd_w");
@@ -952,16 +943,38 @@ __global__ void __launch_bounds__(256) k_gattr(int64_t E, int nrb, int H, int Hp
   }
 }
 
-// g_rvec_e = alpha x_e g_v'[dst_e]   (v'_i = v_i + alpha sum x_e rvec_e)
-__global__ void k_edge_grvec(int64_t E, const int32_t* __restrict__ dst, const float* __restrict__ xe,
-                             const float* __restrict__ g_v, float alpha, float* __restrict__ g_rvec) {
-  const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (e >= E) return;
-  const size_t i = (size_t)dst[e];
-  const float t = alpha * xe[e];
-  g_rvec[3 * e] = t * g_v[3 * i];
-  g_rvec[3 * e + 1] = t * g_v[3 * i + 1];
-  g_rvec[3 * e + 2] = t * g_v[3 * i + 2];
+// g_rvec_e = alpha x_e g_v'[dst_e] with x_e = wx . silu(z2_e)   (v'_i = v_i + alpha sum x_e rvec_e).
+// One wavefront per 16 edges: lane (g, x) reads the T fragments of the group, slot u is edge tset_row(rb16, g, u);
+// the eight sums over the 32 lanes of a half share one butterfly, each exchange halving the slots a lane still
+// carries (9 exchanges instead of 40); lane bits 4, 3, 2 of x end up naming the slot the lane holds.
+__global__ void __launch_bounds__(256) k_edge_grvec(int64_t E, int nrb16, int ncb, int H, const char* __restrict__ z2_T,
+                                                    const float* __restrict__ wx, const int32_t* __restrict__ dst,
+                                                    const float* __restrict__ g_v, float alpha,
+                                                    float* __restrict__ g_rvec) {
+  const int lane = threadIdx.x & 63, g = lane >> 5, x = lane & 31;
+  const int rb16 = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (rb16 >= nrb16) return;
+  float y[8] = {};
+#pragma unroll 4
+  for (int cb = 0; cb < ncb; ++cb) {   // ncb is a multiple of 4
+    const float w = cb * 32 + x < H ? wx[cb * 32 + x] : 0.f;
+    float zz[8];
+    unpack8(*reinterpret_cast<const uint4*>(z2_T + (((long)rb16 * ncb + cb) * 64 + lane) * 16), zz);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) y[u] = fmaf(w, silu_f(zz[u]), y[u]);
+  }
+  const bool b4 = x & 16, b3 = x & 8, b2 = x & 4;
+  float a4[4], a2[2];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) a4[q] = (b4 ? y[4 + q] : y[q]) + __shfl_xor(b4 ? y[q] : y[4 + q], 16);
+#pragma unroll
+  for (int q = 0; q < 2; ++q) a2[q] = (b3 ? a4[2 + q] : a4[q]) + __shfl_xor(b3 ? a4[q] : a4[2 + q], 8);
+  float t = (b2 ? a2[1] : a2[0]) + __shfl_xor(b2 ? a2[0] : a2[1], 4);
+  t += __shfl_xor(t, 2);
+  t += __shfl_xor(t, 1);
+  const long e = tset_row(rb16, g, (x >> 2) & 7);
+  const int c = x & 3;
+  if (c < 3 && e < E) g_rvec[3 * e + c] = alpha * t * g_v[3 * (size_t)dst[e] + c];
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1007,7 +1020,6 @@ struct WideSaved {
   float* z3;            // [Np, Hp]
   char* hM_T;           // [Np, 2 Hp] T fragments of [h ; M]     (operands of the reverse pass's weight gradients)
   char* a3_T;           // [Np, Hp] T fragments of silu(z3)
-  float* xe;            // [Ep] wx . m_e
   size_t bytes;
 };
 static WideSaved carve_saved_w(void* p, const WideDims& d) {
@@ -1021,7 +1033,6 @@ static WideSaved carve_saved_w(void* p, const WideDims& d) {
   s.z3 = c.take<float>((size_t)d.Np * d.Hp);
   s.hM_T = c.take<char>(d.node_frag_bytes(2));
   s.a3_T = c.take<char>(d.node_frag_bytes(1));
-  s.xe = c.take<float>((size_t)d.Ep);
   s.bytes = c.used();
   return s;
 }
@@ -1229,7 +1240,7 @@ int32_t wide_layer_fwd(hipStream_t st, const WideLayerArgs& a) {
     g.bias = W + o.b2; g.nbias = H;
     HGNN_TRY(launch_fgemm_rows_T(st, g));
   }
-  HGNN_TRY(launch_seg_fwd_w(st, Hp, d.N, a.row_ptr, s.z2_T, a.rvec, W + o.wx, H, a.alpha, a.v_in, s.M, a.v_out, s.xe));
+  HGNN_TRY(launch_seg_fwd_w(st, Hp, d.N, a.row_ptr, s.z2_T, a.rvec, W + o.wx, H, a.alpha, a.v_in, s.M, a.v_out));
   {  // M -> second half of the [h ; M] operand
     ToFragArgs t;
     t.X = s.M; t.ldx = Hp; t.M = d.N; t.Mp = d.Np; t.ncol = Hp; t.Cp = Hp;
@@ -1369,7 +1380,9 @@ int32_t wide_layer_bwd(hipStream_t st, const WideLayerArgs& a) {
   }
   if (a.g_rvec && d.E > 0) {
     ProfScope ps(PT_MISC, st);
-    k_edge_grvec<<<(unsigned)((d.E + 255) / 256), 256, 0, st>>>(d.E, a.dst, s.xe, a.g_v_out, a.alpha, a.g_rvec);
+    const int nrb16 = (int)(d.Ep / 16);
+    k_edge_grvec<<<(unsigned)((nrb16 + 3) / 4), 256, 0, st>>>(d.E, nrb16, d.ncb, H, s.z2_T, W + o.wx, a.dst, a.g_v_out,
+                                                              a.alpha, a.g_rvec);
     HGNN_LAUNCH_CHECK("k_edge_grvec");
   }
   // g_P, g_Q: per-atom sums of g_z1 over the destination-sorted and the source-sorted lists

@@ -37,11 +37,14 @@ def make_weights(seed, H, L, S, N, G, Hh=None, D=None, k=1):
     return emb, Ws, Wh, gE, gF
 
 
-def problem_from_config(name, rbf_k=None, **over):
-    """rbf_k: run the config with that many radial-basis edge attributes in place of d2."""
+def problem_from_config(name, rbf_k=None, move=False, pos_grad=False, **over):
+    """rbf_k: run the config with that many radial-basis edge attributes in place of d2. move: the atoms move between
+    layers; pos_grad: the reverse pass also gives the position gradient."""
     batch, hp = make_config(name, **over)
     if rbf_k:
         hp["rbf_k"] = int(rbf_k)
+    if move or pos_grad:
+        hp.update(move=bool(move), pos_grad=True)
     emb, Ws, Wh, gE, gF = make_weights(hp["seed"], hp["H"], hp["L"], hp["S"], batch.N, batch.G, hp.get("Hh"),
                                        hp.get("D"), hp.get("rbf_k") or 1)
     return dict(batch=batch, hp=hp, emb=emb, Ws=Ws, Wh=Wh, gE=gE, gF=gF)
