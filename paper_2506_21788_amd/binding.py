@@ -27,7 +27,7 @@ EXPORTS = [
     "hgnn_multihead_plan_ints", "hgnn_multihead_plan",
     "hgnn_multihead_decode_workspace_bytes", "hgnn_multihead_decode_fwd", "hgnn_multihead_decode_bwd",
     "hgnn_multihead_deep_workspace_bytes", "hgnn_multihead_deep_fwd", "hgnn_multihead_deep_bwd",
-    "hgnn_adamw_step", "hgnn_mfma_probe",
+    "hgnn_adamw_step", "hgnn_mfma_probe", "hgnn_load_probe",
     "hgnn_profile_begin", "hgnn_profile_end", "hgnn_profile_num_tags", "hgnn_profile_tag_name",
     "hgnn_profile_read",
 ]
@@ -311,6 +311,14 @@ def mfma_probe(dtype, workgroups, iters, sink):
     """Launch the matrix-core rate probe; returns the floating-point operations of the launch."""
     _lib.hgnn_mfma_probe.restype = C.c_int64
     return int(_lib.hgnn_mfma_probe(_stream(), C.c_int32(dtype), C.c_int32(workgroups), C.c_int32(iters), _p(sink)))
+
+
+def load_probe(kind, workgroups, iters, window_chunks, buf, sink):
+    """Launch the load-path rate probe; returns the bytes the launch loads."""
+    _lib.hgnn_load_probe.restype = C.c_int64
+    return int(_lib.hgnn_load_probe(_stream(), C.c_int32(kind), C.c_int32(workgroups), C.c_int32(iters),
+                                    C.c_int64(window_chunks), _p(buf), C.c_int64(0 if buf is None else buf.numel() * buf.element_size()),
+                                    _p(sink)))
 
 
 def profile_begin(tag_mask):

@@ -146,3 +146,72 @@ extern "C" int64_t hgnn_mfma_probe(void* stream, int32_t dtype, int32_t workgrou
   const int64_t per_instr = bf16 ? 2LL * 32 * 32 * 16 : 2LL * 32 * 32 * 2;
   return (int64_t)workgroups * 4 /*wavefronts*/ * iters * 4 * per_instr;
 }
+
+// ---------------------------------------------------------------------------------------------
+// Load-path rate probe (instrumentation): what the vector memory path (16-byte loads per lane, 1 KiB per wavefront
+// instruction, eight in flight) and the LDS (ds_read_b128) deliver per compute unit, to set beside the operand
+// traffic of the matrix kernels.
+// kind 0: wavefront w reads the 1 KiB chunks (first + 8 it + u) mod window of a device buffer, first = w * window
+//         (window == 0: the whole buffer, first = w * 8): small windows stay in the L1, buffers of a few MB in the L2
+// kind 1: every wavefront reads eight 1 KiB pieces of a 32 KiB LDS array per round
+// ---------------------------------------------------------------------------------------------
+namespace hgnn {
+typedef unsigned probe_u32x4 __attribute__((ext_vector_type(4)));
+
+__global__ void __launch_bounds__(256) k_load_probe_global(int iters, long window, const char* __restrict__ buf,
+                                                           long nchunks, unsigned* sink) {
+  const int lane = threadIdx.x & 63;
+  const long w = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const long span = window > 0 ? window : nchunks;
+  const long first = window > 0 ? (w * window) % nchunks : (w * 8) % nchunks;
+  probe_u32x4 acc = {0u, 0u, 0u, 0u};
+  long pos = 0;
+  for (int it = 0; it < iters; ++it) {
+    probe_u32x4 v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      long c = first + (pos + u) % span;
+      if (c >= nchunks) c -= nchunks;
+      v[u] = *reinterpret_cast<const probe_u32x4*>(buf + c * 1024 + lane * 16);
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc ^= v[u];
+    pos = (pos + 8) % span;
+  }
+  if ((acc[0] ^ acc[1] ^ acc[2] ^ acc[3]) == 0x9e3779b9u) sink[0] = acc[0];   // keeps the loads alive
+}
+
+__global__ void __launch_bounds__(256) k_load_probe_lds(int iters, unsigned* sink) {
+  __shared__ __align__(16) probe_u32x4 lds[2048];   // 32 KiB
+  for (int i = threadIdx.x; i < 2048; i += 256) lds[i] = probe_u32x4{(unsigned)i, 1u, 2u, 3u};
+  __syncthreads();
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  probe_u32x4 acc = {0u, 0u, 0u, 0u};
+  for (int it = 0; it < iters; ++it) {
+    probe_u32x4 v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = lds[((it + wave * 8 + u * 4) & 31) * 64 + lane];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc ^= v[u];
+  }
+  if ((acc[0] ^ acc[1] ^ acc[2] ^ acc[3]) == 0x9e3779b9u) sink[0] = acc[0];
+}
+}  // namespace hgnn
+
+extern "C" int64_t hgnn_load_probe(void* stream, int32_t kind, int32_t workgroups, int32_t iters, int64_t window_chunks,
+                                   const void* buf, int64_t buf_bytes, void* sink) {
+  if (workgroups <= 0 || iters <= 0 || !sink || window_chunks < 0) return 0;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (kind == 0) {
+    const long nchunks = buf_bytes / 1024;
+    if (!buf || nchunks < 8 || window_chunks > nchunks || (window_chunks > 0 && window_chunks < 8)) return 0;
+    hgnn::k_load_probe_global<<<dim3((unsigned)workgroups), 256, 0, st>>>(iters, window_chunks, static_cast<const char*>(buf),
+                                                                          nchunks, static_cast<unsigned*>(sink));
+  } else if (kind == 1) {
+    hgnn::k_load_probe_lds<<<dim3((unsigned)workgroups), 256, 0, st>>>(iters, static_cast<unsigned*>(sink));
+  } else {
+    return 0;
+  }
+  if (hipGetLastError() != hipSuccess) return 0;
+  return (int64_t)workgroups * 4 * iters * 8 * 1024;
+}

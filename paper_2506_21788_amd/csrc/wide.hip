@@ -313,6 +313,149 @@ static int32_t launch_fgemm_t(hipStream_t st, const FGemmArgs& a) {
   return HGNN_OK;
 }
 
+// Row product with the result as T fragments, tile 256 x 128, A fragments straight from memory into registers:
+// wavefront w owns row blocks i0 + 2 w, + 1 and all four column blocks, so nobody else needs its A fragments. A sits
+// in a register ring of four steps, asked for three steps ahead; only B (shared by the four wavefronts) passes
+// through the LDS: per matrix-core instruction half an LDS fragment read instead of three quarters and a third of
+// the LDS writes. Steps of 32 k, four per loop body (the contraction is a multiple of 128).
+// (Measured against this: the same kernel with eight wavefronts on a 256 x 256 tile, which loads a third fewer
+// operand bytes per flop, runs 12 - 20 % slower: one workgroup per compute unit leaves nothing to run while its
+// wavefronts meet at the barrier; with 128 x 128 tiles and three workgroups per compute unit it runs 20 % slower.)
+__global__ void __launch_bounds__(256, 2) k_fgemm_ad(FGemmArgs p) {
+  constexpr int NW = 4, WI = 2, WJ = 4, KC = 2, TI = 8, TJ = 4;
+  constexpr int STAGE = KC * TJ * 64;   // 16-byte units of B per step
+  __shared__ __align__(16) u32x4_t lds[2 * STAGE];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wi = wave, wj = 0;
+  const int xcd = blockIdx.x & 7, q = blockIdx.x >> 3;
+  const int nTj = p.nJ / TJ;
+  const int ti = (q / nTj) * 8 + xcd, tj = q % nTj;   // the column tiles of a row tile share an XCD (one L2)
+  if (ti >= p.nI / TI) return;                         // uniform over the workgroup, before any barrier
+  const int i0 = ti * TI, j0 = tj * TJ;
+  const int nch = p.nkb / KC;
+  auto kclamp = [&](int ch) { return (long)(ch < nch ? ch : nch - 1) * KC; };
+
+  const char* asrc[WI];
+#pragma unroll
+  for (int i = 0; i < WI; ++i) asrc[i] = p.A + (long)(i0 + wi * WI + i) * p.a_si * 1024 + lane * 16;
+  const long akst = p.a_sk * 1024;
+  // B: pass s copies fragment f = NW s + wave of the step's KC x TJ fragments (kk = f / TJ, jj = f % TJ)
+  const char* bsrc[2];
+#pragma unroll
+  for (int s = 0; s < 2; ++s) {
+    const int f = NW * s + wave, kk = f / TJ, jj = f % TJ;
+    bsrc[s] = p.B + ((long)(j0 + jj) * p.b_sj + (long)kk * p.b_sk) * 1024 + lane * 16;
+  }
+  const long bkst = p.b_sk * 1024;
+
+  f32x16_t acc[WI][WJ];
+#pragma unroll
+  for (int i = 0; i < WI; ++i)
+#pragma unroll
+    for (int j = 0; j < WJ; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  // (the B loads come first: the compiler merges the load counts of this prologue into the loop's own, and fewer
+  // loads behind Y here than in the loop would make every iteration wait for nearly all of its loads)
+  u32x4_t aR[4][KC][WI], preX[2], preY[2];
+  {
+    const long k0 = kclamp(0), k1 = kclamp(1);
+#pragma unroll
+    for (int s = 0; s < 2; ++s) preX[s] = *reinterpret_cast<const u32x4_t*>(bsrc[s] + k0 * bkst);
+#pragma unroll
+    for (int s = 0; s < 2; ++s) preY[s] = *reinterpret_cast<const u32x4_t*>(bsrc[s] + k1 * bkst);
+  }
+#pragma unroll
+  for (int st = 0; st < 3; ++st) {
+    const long k0 = kclamp(st);
+#pragma unroll
+    for (int kk = 0; kk < KC; ++kk)
+#pragma unroll
+      for (int i = 0; i < WI; ++i) aR[st][kk][i] = *reinterpret_cast<const u32x4_t*>(asrc[i] + (k0 + kk) * akst);
+  }
+  {
+    const long k2 = kclamp(2);
+#pragma unroll
+    for (int s = 0; s < 2; ++s) lds[(NW * s + wave) * 64 + lane] = preX[s];
+#pragma unroll
+    for (int s = 0; s < 2; ++s) preX[s] = *reinterpret_cast<const u32x4_t*>(bsrc[s] + k2 * bkst);
+  }
+  __syncthreads();
+  // after the prologue: LDS half 0 = B of step 0, Y = B of step 1, X = B of step 2, aR[0..2] = A of steps 0..2
+  for (int c = 0; c < nch; c += 4) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int half = r & 1;
+      const u32x4_t* cur = lds + half * STAGE;
+#pragma unroll
+      for (int kk = 0; kk < KC; ++kk) {
+        bf16x8_t b[WJ];
+#pragma unroll
+        for (int j = 0; j < WJ; ++j) b[j] = __builtin_bit_cast(bf16x8_t, cur[(kk * TJ + wj * WJ + j) * 64 + lane]);
+#pragma unroll
+        for (int i = 0; i < WI; ++i)
+#pragma unroll
+          for (int j = 0; j < WJ; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, aR[r][kk][i]), b[j],
+                                                                acc[i][j], 0, 0, 0);
+      }
+      const long kn = kclamp(c + r + 3);
+#pragma unroll
+      for (int kk = 0; kk < KC; ++kk)
+#pragma unroll
+        for (int i = 0; i < WI; ++i)
+          aR[(r + 3) & 3][kk][i] = *reinterpret_cast<const u32x4_t*>(asrc[i] + (kn + kk) * akst);
+      if (half == 0) {
+#pragma unroll
+        for (int s = 0; s < 2; ++s) lds[STAGE + (NW * s + wave) * 64 + lane] = preY[s];
+#pragma unroll
+        for (int s = 0; s < 2; ++s) preY[s] = *reinterpret_cast<const u32x4_t*>(bsrc[s] + kn * bkst);
+      } else {
+#pragma unroll
+        for (int s = 0; s < 2; ++s) lds[(NW * s + wave) * 64 + lane] = preX[s];
+#pragma unroll
+        for (int s = 0; s < 2; ++s) preX[s] = *reinterpret_cast<const u32x4_t*>(bsrc[s] + kn * bkst);
+      }
+      __syncthreads();
+    }
+  }
+  const int x = lane & 31;
+#pragma unroll
+  for (int j = 0; j < WJ; ++j) {
+    const int jb = j0 + wj * WJ + j;
+    const int colx = jb * 32 + x;
+    float bv = 0.f;
+    if (p.bias && colx < p.nbias) bv = p.bias[colx];
+#pragma unroll
+    for (int i = 0; i < WI; ++i) {
+      const int ib = i0 + wi * WI + i;
+#pragma unroll
+      for (int hh = 0; hh < 2; ++hh) {
+        uint4 w;
+        w.x = pack_bf16x2(acc[i][j][8 * hh + 0] + bv, acc[i][j][8 * hh + 1] + bv);
+        w.y = pack_bf16x2(acc[i][j][8 * hh + 2] + bv, acc[i][j][8 * hh + 3] + bv);
+        w.z = pack_bf16x2(acc[i][j][8 * hh + 4] + bv, acc[i][j][8 * hh + 5] + bv);
+        w.w = pack_bf16x2(acc[i][j][8 * hh + 6] + bv, acc[i][j][8 * hh + 7] + bv);
+        *reinterpret_cast<uint4*>(p.T + ((long)(2 * ib + hh) * p.t_ncb + jb) * 1024 + lane * 16) = w;
+      }
+    }
+  }
+}
+
+static int32_t launch_fgemm_ad(hipStream_t st, const FGemmArgs& a) {
+  HGNN_REQUIRE(a.nI % 8 == 0 && a.nJ % 4 == 0 && a.nkb % 8 == 0 && a.nkb > 0 && !a.grp_ptr && a.nsplit == 1 && a.kper == a.nkb,
+               HGNN_ERR_BAD_SHAPE, "fragment GEMM: %d x %d blocks, %d contraction blocks do not tile", a.nI, a.nJ, a.nkb);
+  if (a.nI == 0 || a.nJ == 0) return HGNN_OK;
+  const long gx = (a.nI / 8 + 7) / 8 * 8 * (long)(a.nJ / 4);
+  HGNN_REQUIRE(gx <= 2147483647L, HGNN_ERR_OVERFLOW, "fragment GEMM: grid too large");
+  ProfScope ps(a.tag, st);
+  k_fgemm_ad<<<dim3((unsigned)gx), 256, 0, st>>>(a);
+  HGNN_LAUNCH_CHECK("k_fgemm_ad");
+  return HGNN_OK;
+}
+
 // ---------------------------------------------------------------------------------------------
 // weights -> B fragments:  fragment (nb, kb) of the destination, lane (g, x), slot u  =  B[16 kb + 8 g + u][32 nb + x]
 // ---------------------------------------------------------------------------------------------
@@ -1161,7 +1304,7 @@ int32_t launch_fgemm_rows(hipStream_t st, const FGemmArgs& a0) {
 }
 // (256 x 256 tiles move a third less through the L2 but measured slower than two resident 256 x 128 workgroups of four
 // wavefronts: by 15 % with one workgroup of four wavefronts per CU, by 6 % with one of eight, NW = 8 below)
-int32_t launch_fgemm_rows_T(hipStream_t st, const FGemmArgs& a) { return launch_fgemm_t<4, 2, EPI_T>(st, a); }
+int32_t launch_fgemm_rows_T(hipStream_t st, const FGemmArgs& a) { return launch_fgemm_ad(st, a); }
 
 // layer-level shorthand: square Hp blocks, no groups
 static int32_t wgrad_w(hipStream_t st, const WideDims& d, const char* A_T, int a_ncb, int a_cb0, int nI, const char* B_T,
