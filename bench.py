@@ -123,8 +123,8 @@ def calib_load():
     import torch
     from paper_2506_21788_amd import binding as B
     sink = torch.zeros(4, dtype=torch.int32, device="cuda")
-    cases = {"l1_window_16KiB": (0, 16, 1 << 26), "l2_buffer_2MiB": (0, 0, 1 << 21), "l2_buffer_16MiB": (0, 0, 1 << 24),
-             "mall_buffer_128MiB": (0, 0, 1 << 27), "hbm_buffer_2GiB": (0, 0, 1 << 31), "lds": (1, 0, 0)}
+    cases = {"l1_shared_16KiB": (0, -16, 1 << 21), "l2_buffer_2MiB": (0, 0, 1 << 21), "l2_buffer_16MiB": (0, 0, 1 << 24),
+             "mall_buffer_128MiB": (0, 0, 1 << 27), "hbm_buffer_4GiB": (0, 0, 1 << 32), "lds": (1, 0, 0)}
     out = {}
     for name, (kind, window, nbytes) in cases.items():
         buf = torch.zeros(nbytes // 4, dtype=torch.int32, device="cuda") if nbytes else None

@@ -340,9 +340,10 @@ int64_t hgnn_mfma_probe(void* stream, int32_t dtype, int32_t workgroups, int32_t
 
 /* Load-path rate probe (instrumentation): `workgroups` x 4 wavefronts each issue 8 * iters loads of 1 KiB (16 bytes
  * per lane, eight in flight) and the call returns the bytes that launch loads (0 on a bad argument or launch failure).
- * kind 0: from the device buffer buf (buf_bytes, a multiple of 1 KiB, at least 8 KiB); wavefront w walks the chunks
- *         w * window .. + window - 1 cyclically (window_chunks >= 8: a window of 16 stays in the L1, a buffer of a few MB
- *         in the L2), or the whole buffer from chunk 8 w on (window_chunks == 0);
+ * kind 0: from the device buffer buf (buf_bytes, a multiple of 1 KiB, at least 8 KiB); wavefront w walks cyclically
+ *         the chunks w * window .. + window - 1 (window_chunks >= 8), its equal share of the buffer (window_chunks == 0:
+ *         a buffer far larger than the caches streams from HBM, one of a few MB stays in the L2), or the first
+ *         -window_chunks chunks, the same for every wavefront (window_chunks <= -8: they stay in the L1);
  * kind 1: from a 32 KiB LDS array (buf unused).
  * The caller times it; `sink` is one device word that is never written in practice. Only enqueues work. */
 int64_t hgnn_load_probe(void* stream, int32_t kind, int32_t workgroups, int32_t iters, int64_t window_chunks,

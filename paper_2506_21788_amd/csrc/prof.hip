@@ -151,8 +151,9 @@ extern "C" int64_t hgnn_mfma_probe(void* stream, int32_t dtype, int32_t workgrou
 // Load-path rate probe (instrumentation): what the vector memory path (16-byte loads per lane, 1 KiB per wavefront
 // instruction, eight in flight) and the LDS (ds_read_b128) deliver per compute unit, to set beside the operand
 // traffic of the matrix kernels.
-// kind 0: wavefront w reads the 1 KiB chunks (first + 8 it + u) mod window of a device buffer, first = w * window
-//         (window == 0: the whole buffer, first = w * 8): small windows stay in the L1, buffers of a few MB in the L2
+// kind 0: wavefront w reads 1 KiB chunks of a device buffer cyclically: window > 0: chunks w * window .. + window - 1;
+//         window == 0: its equal share of the buffer (a buffer far larger than the caches streams from HBM, one of a
+//         few MB stays in the L2); window < 0: every wavefront the same first -window chunks (they stay in the L1)
 // kind 1: every wavefront reads eight 1 KiB pieces of a 32 KiB LDS array per round
 // ---------------------------------------------------------------------------------------------
 namespace hgnn {
@@ -162,8 +163,10 @@ __global__ void __launch_bounds__(256) k_load_probe_global(int iters, long windo
                                                            long nchunks, unsigned* sink) {
   const int lane = threadIdx.x & 63;
   const long w = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
-  const long span = window > 0 ? window : nchunks;
-  const long first = window > 0 ? (w * window) % nchunks : (w * 8) % nchunks;
+  const long nwaves = (long)gridDim.x * 4;
+  const long own = nchunks / nwaves >= 8 ? nchunks / nwaves : 8;       // window == 0: an equal share of the buffer
+  const long span = window > 0 ? window : window < 0 ? -window : own;
+  const long first = window > 0 ? (w * window) % nchunks : window < 0 ? 0 : (w * own) % nchunks;
   probe_u32x4 acc = {0u, 0u, 0u, 0u};
   long pos = 0;
   for (int it = 0; it < iters; ++it) {
@@ -200,11 +203,12 @@ __global__ void __launch_bounds__(256) k_load_probe_lds(int iters, unsigned* sin
 
 extern "C" int64_t hgnn_load_probe(void* stream, int32_t kind, int32_t workgroups, int32_t iters, int64_t window_chunks,
                                    const void* buf, int64_t buf_bytes, void* sink) {
-  if (workgroups <= 0 || iters <= 0 || !sink || window_chunks < 0) return 0;
+  if (workgroups <= 0 || iters <= 0 || !sink) return 0;
   hipStream_t st = static_cast<hipStream_t>(stream);
   if (kind == 0) {
     const long nchunks = buf_bytes / 1024;
-    if (!buf || nchunks < 8 || window_chunks > nchunks || (window_chunks > 0 && window_chunks < 8)) return 0;
+    const long aw = window_chunks < 0 ? -window_chunks : window_chunks;
+    if (!buf || nchunks < 8 || aw > nchunks || (aw > 0 && aw < 8)) return 0;
     hgnn::k_load_probe_global<<<dim3((unsigned)workgroups), 256, 0, st>>>(iters, window_chunks, static_cast<const char*>(buf),
                                                                           nchunks, static_cast<unsigned*>(sink));
   } else if (kind == 1) {

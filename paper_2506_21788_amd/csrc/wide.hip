@@ -1302,8 +1302,6 @@ int32_t launch_fgemm_rows(hipStream_t st, const FGemmArgs& a0) {
   if (big_tiles < 4L * num_cus()) return launch_fgemm_t<2, 2, EPI_ROW>(st, a);
   return launch_fgemm_t<4, 2, EPI_ROW>(st, a);
 }
-// (256 x 256 tiles move a third less through the L2 but measured slower than two resident 256 x 128 workgroups of four
-// wavefronts: by 15 % with one workgroup of four wavefronts per CU, by 6 % with one of eight, NW = 8 below)
 int32_t launch_fgemm_rows_T(hipStream_t st, const FGemmArgs& a) { return launch_fgemm_ad(st, a); }
 
 // layer-level shorthand: square Hp blocks, no groups
