@@ -95,3 +95,29 @@ def test_host_side_argument_checks_need_no_gpu():
     assert hw(64, 0) == code and hw(64, 1) == 0 and hw(2000, 1) == -2 and hw(128, 0) == 0
     lib.hgnn_multihead_plan_ints.restype = ctypes.c_int64
     assert lib.hgnn_multihead_plan_ints(ctypes.c_int32(7), ctypes.c_int32(3), ctypes.c_int32(2)) >= 2 * 3 + 7 + 3 + 3
+
+
+def test_geometry_entry_points_check_their_arguments_on_the_host():
+    lib = ctypes.CDLL(LIB)
+    lib.hgnn_last_error_string.restype = ctypes.c_char_p
+    nullptr_code = int(re.search(r"HGNN_ERR_NULLPTR\s*=\s*(-?\d+)", open(HEADER).read()).group(1))
+    i32, i64, f32, vp = ctypes.c_int32, ctypes.c_int64, ctypes.c_float, ctypes.c_void_p
+    fake = lambda n: vp(0x1000 * n)     # never dereferenced: every call below returns before any launch
+    # radial basis and its reverse: 2 <= k <= 16, rc > 0
+    assert lib.hgnn_edge_rbf_bwd(None, i64(10), fake(1), i32(1), f32(5.0), fake(2), fake(3)) == -2
+    assert lib.hgnn_edge_rbf_bwd(None, i64(10), fake(1), i32(17), f32(5.0), fake(2), fake(3)) == -2
+    assert lib.hgnn_edge_rbf_bwd(None, i64(10), fake(1), i32(4), f32(0.0), fake(2), fake(3)) == -2
+    assert lib.hgnn_edge_rbf_bwd(None, i64(-1), fake(1), i32(4), f32(5.0), fake(2), fake(3)) == -2
+    assert lib.hgnn_edge_rbf_bwd(None, i64(0), None, i32(4), f32(5.0), None, None) == 0          # nothing to do
+    assert lib.hgnn_edge_rbf_bwd(None, i64(10), fake(1), i32(4), f32(5.0), None, fake(3)) == nullptr_code
+    # geometry: forward needs every array, the reverse pass needs rvec only with g_d2 and the index arrays only with g_v
+    assert lib.hgnn_edge_geometry_fwd(None, i32(5), i64(0), None, None, None, None, None, None) == 0
+    assert lib.hgnn_edge_geometry_fwd(None, i32(5), i64(10), fake(1), None, fake(2), fake(3), fake(4), fake(5)) == nullptr_code
+    assert lib.hgnn_edge_geometry_fwd(None, i32(-1), i64(10), fake(1), fake(6), fake(2), fake(3), fake(4), fake(5)) == -2
+    bwd = lib.hgnn_edge_geometry_bwd
+    assert bwd(None, i32(5), i64(0), None, None, None, None, None, None, None, None, None) == 0
+    assert bwd(None, i32(5), i64(10), None, None, None, None, fake(1), fake(2), fake(3), None, None) == nullptr_code  # g_d2 without rvec
+    assert bwd(None, i32(5), i64(10), None, None, None, fake(4), fake(1), fake(2), fake(3), None, fake(5)) == nullptr_code  # g_v without index arrays
+    assert bwd(None, i32(5), i64(10), None, None, None, fake(4), fake(1), fake(2), fake(3), fake(3), None) == -2     # g_r_sum aliases g_r
+    assert b"alias" in lib.hgnn_last_error_string()
+    assert bwd(None, i32(5), i64(2 ** 31), None, None, None, fake(4), fake(1), fake(2), fake(3), None, None) == -7   # 3 E overflows
