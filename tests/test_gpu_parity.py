@@ -295,20 +295,27 @@ def test_side_stream_on_and_off_give_the_same_bits(which):
             assert np.array_equal(a.view(np.uint32), c.view(np.uint32))
 
 
-@pytest.mark.parametrize("name", ["cfg1", "cfg3", "paper-shape"])
+@pytest.mark.parametrize("name", ["cfg1", "cfg3", "paper-shape", "moving-atoms"])
 def test_hip_graph_replays_match_eager_bitwise(name):
     """forward + backward recorded into a HIP graph: every replay, with eager work and synchronisations between
     the replays, gives the bits of the eager step."""
     say(f"hip graph {name}")
     import torch
-    P = _paper_shape_small() if name == "paper-shape" else problem_from_config(name)
+    if name == "paper-shape":
+        P = _paper_shape_small()
+    elif name == "moving-atoms":   # per-layer geometry, radial basis, position gradients: their kernels and fills too
+        b = small_mixed_batch(31, n_mol=5, n_cry=4, S=3, mol_atoms=(3, 40), cry_atoms=(2, 30))
+        P = problem_from_batch(b, 4.5, 200, 3, 3, "bf16", seed=31, rbf_k=6, move=True)
+    else:
+        P = problem_from_config(name)
     gE, gF = torch.as_tensor(P["gE"]).cuda(), torch.as_tensor(P["gF"]).cuda()
     hpth = gpu_hotpath(P)
     hpth.build_graph()
 
     def outputs():
         torch.cuda.synchronize()
-        return [t.cpu().numpy().copy() for t in (hpth.energy, hpth.force, hpth.gWhead, hpth.g_emb, hpth.g_h0, *hpth.gW)]
+        extra = (hpth.g_pos,) if name == "moving-atoms" else ()
+        return [t.cpu().numpy().copy() for t in (hpth.energy, hpth.force, hpth.gWhead, hpth.g_emb, hpth.g_h0, *hpth.gW, *extra)]
 
     hpth.forward()
     hpth.backward(gE, gF)
