@@ -52,6 +52,7 @@ struct FCfg {
 
 template <int WI, int WJ, int EPI, int NW = 4, int KC = 2>
 __global__ void __launch_bounds__(64 * NW, (WI * WJ <= 8 ? 2 : 1)) k_fgemm(FGemmArgs p) {
+  static_assert(EPI == EPI_ROW || EPI == EPI_PART, "results as T fragments come from k_fgemm_ad");
   using C = FCfg<WI, WJ, NW, KC>;
   extern __shared__ __align__(16) u32x4_t lds[];
   const int tid = threadIdx.x, lane = tid & 63;
@@ -260,28 +261,14 @@ __global__ void __launch_bounds__(64 * NW, (WI * WJ <= 8 ? 2 : 1)) k_fgemm(FGemm
     const int jb = j0 + wj * WJ + j;
     if (jb >= p.nJ) continue;   // partial column tile
     const int colx = jb * 32 + x;
-    float bv = 0.f;
-    if (EPI != EPI_PART && p.bias && colx < p.nbias) bv = p.bias[(long)grp * p.bias_grp_stride + colx];
 #pragma unroll
     for (int i = 0; i < WI; ++i) {
       const int ib = i0 + wi * WI + i;
-      if constexpr (EPI == EPI_T) {
+      float* out = p.P + ((long)grp * p.nsplit + split) * p.split_stride;   // [group][split]
 #pragma unroll
-        for (int hh = 0; hh < 2; ++hh) {
-          uint4 w;
-          w.x = pack_bf16x2(acc[i][j][8 * hh + 0] + bv, acc[i][j][8 * hh + 1] + bv);
-          w.y = pack_bf16x2(acc[i][j][8 * hh + 2] + bv, acc[i][j][8 * hh + 3] + bv);
-          w.z = pack_bf16x2(acc[i][j][8 * hh + 4] + bv, acc[i][j][8 * hh + 5] + bv);
-          w.w = pack_bf16x2(acc[i][j][8 * hh + 6] + bv, acc[i][j][8 * hh + 7] + bv);
-          *reinterpret_cast<uint4*>(p.T + ((long)(2 * ib + hh) * p.t_ncb + jb) * 1024 + lane * 16) = w;
-        }
-      } else {
-        float* out = p.P + ((long)grp * p.nsplit + split) * p.split_stride;   // [group][split]
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int row = ib * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
-          out[(long)row * p.ldp + colx] = acc[i][j][v];
-        }
+      for (int v = 0; v < 16; ++v) {
+        const int row = ib * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
+        out[(long)row * p.ldp + colx] = acc[i][j][v];
       }
     }
   }
