@@ -52,8 +52,9 @@ def kernel_work(tag, N, E, H, dtype):
     # widths other than 64 / 128 / 256 (fragment-GEMM path, bf16): per-edge products run as plain GEMMs over materialised tensors
     if tag == "frag_gemm_edge":      # in: a1 (or g_z2) + W2; out: z2 (or g_a1)
         return 2.0 * EH * H, 2 * EH * b + 2.0 * H * H
-    if tag == "frag_wgrad_edge":     # in: a1, g_z2; out: H x H
-        return 2.0 * EH * H, 2 * EH * b + 4.0 * H * H
+    if tag == "frag_wgrad_edge":     # in: a1, g_z2; out: H x H. The class has two launches per product (the split
+        # product and the ordered sum of its partials): the product's work is spread over both
+        return EH * H, (2 * EH * b + 4.0 * H * H) / 2.0
     if tag == "edge_elementwise":    # three kernels per layer: a1 (out 2 copies), g_z2 (in z2, out 2 copies), g_z1 (in g_a1,
         # out 1 copy) = 7 edge tensors, 36 B of per-edge scalars and 5 gathered atom tensors over 3 launches
         return 0.0, (7 * EH * b + 36.0 * E + 5 * NH * b) / 3.0
