@@ -65,7 +65,7 @@ __global__ void __launch_bounds__(64 * NW, (WI * WJ <= 8 ? 2 : 1)) k_fgemm(FGemm
   const int nTj = (p.nJ + C::TJ - 1) / C::TJ;
   int ti, tj, split = 0;
   if (EPI == EPI_PART) {
-    const int tiles = (p.nI / C::TI) * nTj;
+    const int tiles = ((p.nI + C::TI - 1) / C::TI) * nTj;   // a last row tile may stick out past nI
     const int t = q % tiles;
     split = (q / tiles) * 8 + xcd;     // the launcher makes the split count a multiple of 8
     ti = t / nTj;
@@ -104,7 +104,9 @@ __global__ void __launch_bounds__(64 * NW, (WI * WJ <= 8 ? 2 : 1)) k_fgemm(FGemm
     const int f = NW * s + wave;
     if (f < C::KC * C::TI) {
       const int kk = f / C::TI, ii = f % C::TI;
-      src[s] = p.A + ((long)(i0 + ii) * p.a_si + (long)kk * p.a_sk) * 1024 + lane * 16;
+      // (split partials: row blocks past nI repeat the last one and are never stored)
+      const int ib = (EPI == EPI_PART && i0 + ii >= p.nI) ? p.nI - 1 : i0 + ii;
+      src[s] = p.A + ((long)ib * p.a_si + (long)kk * p.a_sk) * 1024 + lane * 16;
       kst[s] = p.a_sk * 1024;
     } else {
       const int f2 = f - C::KC * C::TI;
@@ -264,6 +266,7 @@ __global__ void __launch_bounds__(64 * NW, (WI * WJ <= 8 ? 2 : 1)) k_fgemm(FGemm
 #pragma unroll
     for (int i = 0; i < WI; ++i) {
       const int ib = i0 + wi * WI + i;
+      if (ib >= p.nI) continue;   // partial row tile
       float* out = p.P + ((long)grp * p.nsplit + split) * p.split_stride;   // [group][split]
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
@@ -278,14 +281,14 @@ template <int WI, int WJ, int EPI, int NW = 4, int KC = 2>
 static int32_t launch_fgemm_t(hipStream_t st, const FGemmArgs& a) {
   using C = FCfg<WI, WJ, NW, KC>;
   // (an even number of steps per workgroup: contraction counts are multiples of two steps)
-  HGNN_REQUIRE(a.nI % C::TI == 0 && (a.nJ % C::TJ == 0 || EPI != EPI_PART) && a.nkb % (2 * C::KC) == 0 &&
+  HGNN_REQUIRE((a.nI % C::TI == 0 || EPI == EPI_PART) && (a.nJ % C::TJ == 0 || EPI != EPI_PART) && a.nkb % (2 * C::KC) == 0 &&
                    a.kper % (2 * C::KC) == 0 && a.kper > 0,
                HGNN_ERR_BAD_SHAPE, "fragment GEMM: %d x %d blocks, %d contraction blocks do not tile", a.nI, a.nJ, a.nkb);
   if (a.nI == 0 || a.nJ == 0) return HGNN_OK;
   HGNN_REQUIRE(EPI == EPI_PART ? (a.nsplit % 8 == 0 && (long)a.nsplit * a.kper >= a.nkb) : (a.nsplit == 1 && a.kper == a.nkb),
                HGNN_ERR_BAD_SHAPE, "fragment GEMM: bad split of the contraction");
   const int groups = a.grp_ptr ? a.S : 1;
-  const long nTi = a.nI / C::TI, nTj = (a.nJ + C::TJ - 1) / C::TJ;
+  const long nTi = (a.nI + C::TI - 1) / C::TI, nTj = (a.nJ + C::TJ - 1) / C::TJ;
   const long gx = EPI == EPI_PART ? (long)a.nsplit * nTi * nTj : (nTi + 7) / 8 * 8 * nTj;
   HGNN_REQUIRE(gx <= 2147483647L && groups <= 65535, HGNN_ERR_OVERFLOW, "fragment GEMM: grid too large");
   static bool lds_set = false;   // the ring may exceed the default dynamic LDS limit: raise it once per variant
@@ -1244,9 +1247,12 @@ int32_t launch_fwgrad(hipStream_t st, const FWgradArgs& a) {
   g.nkb = (int)(a.rows / 16);
   g.grp_ptr = a.grp_ptr; g.S = a.S;
   const int groups = a.grp_ptr ? a.S : 1;
-  // enough splits for about three workgroups per CU, as many as the partial buffer holds
-  const long tiles = (long)(a.nI / 4) * (a.nJ / 4) * groups;
-  long want = (3L * num_cus() + tiles - 1) / tiles;
+  // Long contractions over many rows (the per-edge gradient) take 256 x 128 tiles, which load a quarter fewer operand
+  // bytes per flop (a last row tile may be half empty); everything else 128 x 128 tiles.
+  // Enough splits for about three (two) workgroups per CU, as many as the partial buffer holds.
+  const bool big = !a.grp_ptr && a.nI >= 8 && a.rows >= 65536;
+  const long tiles = big ? (long)((a.nI + 7) / 8) * (a.nJ / 4) : (long)(a.nI / 4) * (a.nJ / 4) * groups;
+  long want = ((big ? 2L : 3L) * num_cus() + tiles - 1) / tiles;
   const long cap = (long)(a.partial_floats / ((size_t)a.nI * 32 * a.nJ * 32 * groups));
   if (want > cap) want = cap;
   if (want > WIDE_MAX_SPLITS) want = WIDE_MAX_SPLITS;
@@ -1262,7 +1268,8 @@ int32_t launch_fwgrad(hipStream_t st, const FWgradArgs& a) {
   g.tag = a.tag;
   HGNN_REQUIRE((size_t)g.nsplit * groups * g.split_stride <= a.partial_floats, HGNN_ERR_WORKSPACE_TOO_SMALL,
                "weight-gradient partials do not fit the workspace");
-  HGNN_TRY((launch_fgemm_t<2, 2, EPI_PART>(st, g)));
+  if (big) HGNN_TRY((launch_fgemm_t<4, 2, EPI_PART>(st, g)));
+  else HGNN_TRY((launch_fgemm_t<2, 2, EPI_PART>(st, g)));
   ProfScope ps(a.tag, st);
   const long n = g.split_stride;
   k_reduce_wgrad<<<dim3((unsigned)((n + 255) / 256), groups), 256, 0, st>>>(

@@ -79,7 +79,11 @@ def test_layer_other_modes_edge_counts(H, dtype, E):
 # to 256): the paper's 866, widths on both sides of the padding steps, odd and small widths, edge counts around the
 # 16 / 32 / 256-row groups.
 @pytest.mark.parametrize("H,N,E", [(866, 300, 5000), (384, 200, 3001), (1024, 257, 777), (866, 40, 0), (320, 513, 9000),
-                                   (500, 64, 256), (866, 5, 17), (333, 100, 1500), (257, 33, 700), (100, 80, 900), (24, 50, 300)])
+                                   (500, 64, 256), (866, 5, 17), (333, 100, 1500), (257, 33, 700), (100, 80, 900), (24, 50, 300),
+                                   # enough edges for the 256 x 128 tiles of the per-edge weight gradient: a ragged
+                                   # last row tile (Hp = 384: 8 + 4 blocks), a single whole one (Hp = 256 is served
+                                   # by the fused kernels, so 200 -> 256), and two whole ones (512)
+                                   (320, 2000, 70001), (200, 1500, 66000), (512, 1800, 65536)])
 def test_layer_wide_widths(H, N, E):
     _run_layer(N=N, E=E, H=H, dtype="bf16", seed=H + E)
 
