@@ -1250,7 +1250,7 @@ int32_t launch_fwgrad(hipStream_t st, const FWgradArgs& a) {
   // Long contractions over many rows (the per-edge gradient) take 256 x 128 tiles, which load a quarter fewer operand
   // bytes per flop (a last row tile may be half empty); everything else 128 x 128 tiles.
   // Enough splits for about three (two) workgroups per CU, as many as the partial buffer holds.
-  const bool big = !a.grp_ptr && a.nI >= 8 && a.rows >= 65536;
+  const bool big = !a.grp_ptr && a.nI >= 8 && a.rows >= 65536;   // (atom-level gradients measured the same either way)
   const long tiles = big ? (long)((a.nI + 7) / 8) * (a.nJ / 4) : (long)(a.nI / 4) * (a.nJ / 4) * groups;
   long want = ((big ? 2L : 3L) * num_cus() + tiles - 1) / tiles;
   const long cap = (long)(a.partial_floats / ((size_t)a.nI * 32 * a.nJ * 32 * groups));
