@@ -125,10 +125,11 @@ def calib_load():
     from paper_2506_21788_amd import binding as B
     sink = torch.zeros(4, dtype=torch.int32, device="cuda")
     cases = {"l1_shared_16KiB": (0, -16, 1 << 21), "l2_buffer_2MiB": (0, 0, 1 << 21), "l2_buffer_16MiB": (0, 0, 1 << 24),
-             "mall_buffer_128MiB": (0, 0, 1 << 27), "hbm_buffer_4GiB": (0, 0, 1 << 32), "lds": (1, 0, 0)}
+             "mall_buffer_128MiB": (0, 0, 1 << 27), "hbm_buffer_4GiB": (0, 0, 1 << 32), "lds": (1, 0, 0),
+             "to_lds_l2_buffer_16MiB": (2, 0, 1 << 24), "to_lds_hbm_buffer_4GiB": (2, 0, 1 << 32)}
     out = {}
     for name, (kind, window, nbytes) in cases.items():
-        buf = torch.zeros(nbytes // 4, dtype=torch.int32, device="cuda") if nbytes else None
+        buf = torch.arange(nbytes // 4, dtype=torch.int32, device="cuda") if nbytes else None
         B.load_probe(kind, 2048, 64, window, buf, sink)
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -138,6 +139,8 @@ def calib_load():
         torch.cuda.synchronize()
         s = e0.elapsed_time(e1) * 1e-3
         out[name] = {"TB_per_s": moved / s / 1e12, "bytes_per_clk_per_cu_at_2.4GHz": moved / s / 256 / 2.4e9}
+        if kind == 2:
+            out[name]["mismatching_lanes"] = int(sink[1].item())
         del buf
     print(json.dumps({"calib_load": out}))
 

@@ -344,8 +344,10 @@ int64_t hgnn_mfma_probe(void* stream, int32_t dtype, int32_t workgroups, int32_t
  *         the chunks w * window .. + window - 1 (window_chunks >= 8), its equal share of the buffer (window_chunks == 0:
  *         a buffer far larger than the caches streams from HBM, one of a few MB stays in the L2), or the first
  *         -window_chunks chunks, the same for every wavefront (window_chunks <= -8: they stay in the L1);
- * kind 1: from a 32 KiB LDS array (buf unused).
- * The caller times it; `sink` is one device word that is never written in practice. Only enqueues work. */
+ * kind 1: from a 32 KiB LDS array (buf unused);
+ * kind 2: as kind 0 with window_chunks == 0, but from memory straight into the LDS without passing through registers;
+ *         the first rounds compare what landed with plain loads and add the number of mismatching lanes to sink[1].
+ * The caller times it; `sink` is two device words, the first never written in practice. Only enqueues work. */
 int64_t hgnn_load_probe(void* stream, int32_t kind, int32_t workgroups, int32_t iters, int64_t window_chunks,
                         const void* buf /*device*/, int64_t buf_bytes, void* sink /*device*/);
 

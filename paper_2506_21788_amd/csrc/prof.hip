@@ -199,6 +199,44 @@ __global__ void __launch_bounds__(256) k_load_probe_lds(int iters, unsigned* sin
   }
   if ((acc[0] ^ acc[1] ^ acc[2] ^ acc[3]) == 0x9e3779b9u) sink[0] = acc[0];
 }
+// kind 2: as kind 0 with window == 0, but the eight 1 KiB chunks of a round go from memory straight into the LDS
+// (16 bytes per lane, lane l of a wavefront lands at its 16 l of the 1 KiB piece), without passing through registers.
+// Every round one piece is compared with a plain load of the same chunk; sink[1] counts the mismatching lanes.
+__global__ void __launch_bounds__(256) k_load_probe_to_lds(int iters, const char* __restrict__ buf, long nchunks,
+                                                           unsigned* sink) {
+  __shared__ __align__(16) probe_u32x4 lds[4 * 8 * 64];   // 8 KiB per wavefront
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const long w = (long)blockIdx.x * 4 + wave;
+  const long nwaves = (long)gridDim.x * 4;
+  const long own = nchunks / nwaves >= 8 ? nchunks / nwaves : 8;
+  const long first = (w * own) % nchunks;
+  probe_u32x4 acc = {0u, 0u, 0u, 0u};
+  unsigned bad = 0;
+  long pos = 0;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      long c = first + (pos + u) % own;
+      if (c >= nchunks) c -= nchunks;
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(buf + c * 1024 + lane * 16),
+                                       (__attribute__((address_space(3))) void*)&lds[(wave * 8 + u) * 64], 16, 0, 0);
+    }
+    __syncthreads();   // waits for the loads of every wavefront
+    const int u = it & 7;
+    const probe_u32x4 got = lds[(wave * 8 + u) * 64 + lane];
+    acc ^= got;
+    if (it < 16) {     // the check costs a second load: first rounds only
+      long c = first + (pos + u) % own;
+      if (c >= nchunks) c -= nchunks;
+      const probe_u32x4 want = *reinterpret_cast<const probe_u32x4*>(buf + c * 1024 + lane * 16);
+      bad += (got[0] != want[0]) | (got[1] != want[1]) | (got[2] != want[2]) | (got[3] != want[3]);
+    }
+    __syncthreads();   // the piece has been read before the next round overwrites it
+    pos = (pos + 8) % own;
+  }
+  if (bad) atomicAdd(&sink[1], bad);
+  if ((acc[0] ^ acc[1] ^ acc[2] ^ acc[3]) == 0x9e3779b9u) sink[0] = acc[0];
+}
 }  // namespace hgnn
 
 extern "C" int64_t hgnn_load_probe(void* stream, int32_t kind, int32_t workgroups, int32_t iters, int64_t window_chunks,
@@ -213,6 +251,11 @@ extern "C" int64_t hgnn_load_probe(void* stream, int32_t kind, int32_t workgroup
                                                                           nchunks, static_cast<unsigned*>(sink));
   } else if (kind == 1) {
     hgnn::k_load_probe_lds<<<dim3((unsigned)workgroups), 256, 0, st>>>(iters, static_cast<unsigned*>(sink));
+  } else if (kind == 2) {
+    const long nchunks = buf_bytes / 1024;
+    if (!buf || nchunks < 8) return 0;
+    hgnn::k_load_probe_to_lds<<<dim3((unsigned)workgroups), 256, 0, st>>>(iters, static_cast<const char*>(buf), nchunks,
+                                                                          static_cast<unsigned*>(sink));
   } else {
     return 0;
   }
