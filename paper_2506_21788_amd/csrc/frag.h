@@ -50,6 +50,24 @@ struct FGemmArgs {
   float* P = nullptr;
   long ldp = 0, split_stride = 0;
   int tag = PT_GEMM_NODE;
+  // launch_fgemm_rows_T only, optional (seg_dst != null): rows are destination-sorted edges and the product is z2.
+  // The kernel then also sums m = silu(z2) per destination atom over each wavefront's strip of 64 rows:
+  //   atoms that lie inside one strip:  seg_M[atom][col] = seg_alpha * sum
+  //   atoms that reach past the strip's end / begin before it:  seg_last / seg_first [strip][col] = sum (unscaled)
+  // and x_e = wx . m_e per edge and column tile:  seg_xe[tile * seg_xe_stride + edge]
+  const int32_t* seg_dst = nullptr;
+  const int32_t* seg_row_ptr = nullptr;
+  const float* seg_wx = nullptr;
+  int seg_H = 0;            // valid columns of wx
+  long seg_E = 0;           // valid rows
+  float seg_alpha = 0.f;
+  float* seg_M = nullptr;
+  long seg_ldm = 0;
+  float* seg_first = nullptr;
+  float* seg_last = nullptr;
+  long seg_ldp = 0;         // pitch of seg_first / seg_last
+  float* seg_xe = nullptr;
+  long seg_xe_stride = 0;
 };
 int32_t launch_fgemm_rows(hipStream_t st, const FGemmArgs& a);     // EPI_ROW, 256 x 128 tiles (128 x 128 for few rows)
 int32_t launch_fgemm_rows_T(hipStream_t st, const FGemmArgs& a);   // EPI_T, 256 x 128 tiles

@@ -1,13 +1,14 @@
 // Message-passing layer for hidden widths other than 64 / 128 / 256 (see wide.h for the operand layouts):
-//   k_fgemm        one kernel for every product: out[i][j] += A(i, kb) x B(j, kb) over 1 KiB fragments staged through
-//                  LDS; epilogues: result as T fragments (edge tensors), row-major fp32 / bf16 with bias and
-//                  residuals (atom tensors), fp32 split partials (weight gradients)
+//   k_fgemm        out[i][j] += A(i, kb) x B(j, kb) over 1 KiB fragments staged through LDS; epilogues: row-major
+//                  fp32 / bf16 with bias and residuals (atom tensors), fp32 split partials (weight gradients)
+//   k_fgemm_ad     the per-edge products (result as T fragments), A fragments straight into registers; the z2 product
+//                  also forms M_i = alpha sum silu(z2) per destination atom and x_e = wx . m_e in its epilogue
+//   k_seg_fwd_fix  the atoms whose edges span several 64-row strips of that epilogue, v'_i = v_i + alpha sum x_e rvec_e
 //   k_pack_frag    fp32 weight slices -> B fragments (zero padded)
 //   k_to_frag      row-major fp32 atom tensor -> R and / or T fragments (optionally silu(x) or x * silu'(z))
 //   k_edge_elem    the three element-wise edge kernels on 32 x 128 tiles: a1 = silu(P[dst] + Q[col] + d2 w1d) -> R, T;
 //                  g_z2 = (alpha g_M[dst] + c_e wx) silu'(z2) -> R, T (+ column sums for g_b2, g_wx);
 //                  g_z1 = g_a1 silu'(z1) -> row-major (+ column sums for g_b1, g_w1d)
-//   k_seg_fwd_w    M_i = alpha sum silu(z2), v'_i = v_i + alpha sum (wx . m_e) rvec_e   (one wavefront per atom)
 //   k_segsum_rows  per-atom sums of g_z1 over the destination-sorted rows and over the source-sorted edge list
 // The layer follows the same algebra as the narrow path: the first edge layer is split by linearity into per-atom
 // products P = h W1a + b1, Q = h W1b that the edges gather.
@@ -311,6 +312,11 @@ static int32_t launch_fgemm_t(hipStream_t st, const FGemmArgs& a) {
 // (Measured against this: the same kernel with eight wavefronts on a 256 x 256 tile, which loads a third fewer
 // operand bytes per flop, runs 12 - 20 % slower: one workgroup per compute unit leaves nothing to run while its
 // wavefronts meet at the barrier; with 128 x 128 tiles and three workgroups per compute unit it runs 20 % slower.)
+// SEG: the rows are destination-sorted edges and the product is z2: the epilogue also forms m = silu(z2), its sums per
+// destination atom over the wavefront's 64 rows and x_e = wx . m_e per edge (see FGemmArgs::seg_*), so that no other
+// kernel has to read z2 in the forward pass. The vector units are idle during the products: the other resident
+// workgroup keeps the matrix cores busy meanwhile.
+template <bool SEG>
 __global__ void __launch_bounds__(256, 2) k_fgemm_ad(FGemmArgs p) {
   constexpr int NW = 4, WI = 2, WJ = 4, KC = 2, TI = 8, TJ = 4;
   constexpr int STAGE = KC * TJ * 64;   // 16-byte units of B per step
@@ -411,13 +417,21 @@ __global__ void __launch_bounds__(256, 2) k_fgemm_ad(FGemmArgs p) {
       __syncthreads();
     }
   }
-  const int x = lane & 31;
+  const int x = lane & 31, g = lane >> 5;
+  const long R0 = (long)(i0 + wi * WI) * 32;   // first row of this wavefront's strip of 64 rows
+  float xe[SEG ? 32 : 1];                      // SEG: wx . m of the rows (i, v) of this lane, index 16 i + v
+  if constexpr (SEG) {
+#pragma unroll
+    for (int q = 0; q < 32; ++q) xe[q] = 0.f;
+  }
 #pragma unroll
   for (int j = 0; j < WJ; ++j) {
     const int jb = j0 + wj * WJ + j;
     const int colx = jb * 32 + x;
     float bv = 0.f;
     if (p.bias && colx < p.nbias) bv = p.bias[colx];
+    float wxv = 0.f;
+    if constexpr (SEG) wxv = colx < p.seg_H ? p.seg_wx[colx] : 0.f;
 #pragma unroll
     for (int i = 0; i < WI; ++i) {
       const int ib = i0 + wi * WI + i;
@@ -429,8 +443,121 @@ __global__ void __launch_bounds__(256, 2) k_fgemm_ad(FGemmArgs p) {
         w.z = pack_bf16x2(acc[i][j][8 * hh + 4] + bv, acc[i][j][8 * hh + 5] + bv);
         w.w = pack_bf16x2(acc[i][j][8 * hh + 6] + bv, acc[i][j][8 * hh + 7] + bv);
         *reinterpret_cast<uint4*>(p.T + ((long)(2 * ib + hh) * p.t_ncb + jb) * 1024 + lane * 16) = w;
+        if constexpr (SEG) {
+          // m = silu of the stored (rounded) z2, as the reverse pass will see it; rows past the last edge give 0
+          const unsigned ww[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+          for (int t = 0; t < 8; ++t) {
+            const int v = 8 * hh + t;
+            const float z = (t & 1) ? bf_hi(ww[t >> 1]) : bf_lo(ww[t >> 1]);
+            const long row = R0 + 32 * i + 8 * (v >> 2) + 4 * g + (v & 3);
+            const float m = row < p.seg_E ? silu_f(z) : 0.f;
+            acc[i][j][v] = m;
+            xe[16 * i + v] = fmaf(wxv, m, xe[16 * i + v]);
+          }
+        }
       }
     }
+  }
+  if constexpr (SEG) {
+    // x_e: the 32 row sums over the 32 lanes of a half share one butterfly, each exchange halving the values a lane
+    // still carries (31 exchanges instead of 160); lane x ends up with the sum of value x = 16 i + v
+    {
+      float a16[16], a8[8], a4[4], a2[2];
+      const bool b4 = x & 16, b3 = x & 8, b2 = x & 4, b1 = x & 2, b0 = x & 1;
+#pragma unroll
+      for (int q = 0; q < 16; ++q) a16[q] = (b4 ? xe[16 + q] : xe[q]) + __shfl_xor(b4 ? xe[q] : xe[16 + q], 16);
+#pragma unroll
+      for (int q = 0; q < 8; ++q) a8[q] = (b3 ? a16[8 + q] : a16[q]) + __shfl_xor(b3 ? a16[q] : a16[8 + q], 8);
+#pragma unroll
+      for (int q = 0; q < 4; ++q) a4[q] = (b2 ? a8[4 + q] : a8[q]) + __shfl_xor(b2 ? a8[q] : a8[4 + q], 4);
+#pragma unroll
+      for (int q = 0; q < 2; ++q) a2[q] = (b1 ? a4[2 + q] : a4[q]) + __shfl_xor(b1 ? a4[q] : a4[2 + q], 2);
+      const float tot = (b0 ? a2[1] : a2[0]) + __shfl_xor(b0 ? a2[0] : a2[1], 1);
+      const int i = x >> 4, v = x & 15;
+      const long row = R0 + 32 * i + 8 * (v >> 2) + 4 * g + (v & 3);
+      if (row < p.seg_E) p.seg_xe[(long)tj * p.seg_xe_stride + row] = tot;
+    }
+    // sums per destination atom over the strip: the atoms of the strip one after the other (rows are sorted by
+    // destination; an atom without edges has an empty range)
+    if (R0 < p.seg_E) {
+      const long Rend = R0 + 64 < p.seg_E ? R0 + 64 : p.seg_E;
+      const int a_first = __builtin_amdgcn_readfirstlane(p.seg_dst[R0]);
+      const int a_last = __builtin_amdgcn_readfirstlane(p.seg_dst[Rend - 1]);
+      const long strip = R0 >> 6;
+      for (int a = a_first; a <= a_last; ++a) {
+        const long e0 = __builtin_amdgcn_readfirstlane(p.seg_row_ptr[a]);
+        const long e1 = __builtin_amdgcn_readfirstlane(p.seg_row_ptr[a + 1]);
+        const int lo = (int)((e0 > R0 ? e0 : R0) - R0), hi = (int)((e1 < R0 + 64 ? e1 : R0 + 64) - R0);
+        if (lo >= hi) continue;
+        float t[WJ];
+#pragma unroll
+        for (int j = 0; j < WJ; ++j) t[j] = 0.f;
+#pragma unroll
+        for (int i = 0; i < WI; ++i)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int rr = 32 * i + 8 * (v >> 2) + (v & 3) + 4 * g;
+            const bool in = (unsigned)(rr - lo) < (unsigned)(hi - lo);
+#pragma unroll
+            for (int j = 0; j < WJ; ++j) t[j] += in ? acc[i][j][v] : 0.f;
+          }
+#pragma unroll
+        for (int j = 0; j < WJ; ++j) t[j] += __shfl_xor(t[j], 32);
+        float* dest;
+        float scale = 1.f;
+        if (e0 < R0) dest = p.seg_first + strip * p.seg_ldp;
+        else if (e1 > R0 + 64) dest = p.seg_last + strip * p.seg_ldp;
+        else { dest = p.seg_M + (long)a * p.seg_ldm; scale = p.seg_alpha; }
+        if (g == 0) {
+#pragma unroll
+          for (int j = 0; j < WJ; ++j) dest[(j0 + wj * WJ + j) * 32 + x] = scale * t[j];
+        }
+      }
+    }
+  }
+}
+
+// Second half of the per-atom sums of the forward pass (one wavefront per atom): M of the atoms whose edges span
+// several 64-row strips from the strips' partial sums, in strip order; zeros for atoms without edges;
+// v'_i = v_i + alpha sum_e x_e rvec_e with x_e the sum of its column tiles' parts (also kept: xe_out[e]).
+__global__ void __launch_bounds__(256) k_seg_fwd_fix(int N, int Hp, int ntj, const int32_t* __restrict__ row_ptr,
+                                                     const float* __restrict__ pfirst, const float* __restrict__ plast,
+                                                     const float* __restrict__ xe_part, long xe_stride,
+                                                     const float* __restrict__ rvec, float alpha,
+                                                     const float* __restrict__ v_in, float* __restrict__ M,
+                                                     float* __restrict__ v_out, float* __restrict__ xe_out) {
+  const int lane = threadIdx.x & 63;
+  const int i = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (i >= N) return;
+  const int e0 = row_ptr[i], e1 = row_ptr[i + 1];
+  if (e0 == e1) {
+    for (int c = lane; c < Hp; c += 64) M[(long)i * Hp + c] = 0.f;
+  } else {
+    const int s0 = e0 >> 6, s1 = (e1 - 1) >> 6;
+    if (s0 != s1) {
+      for (int c = lane; c < Hp; c += 64) {
+        float t = plast[(long)s0 * Hp + c];
+        for (int s = s0 + 1; s <= s1; ++s) t += pfirst[(long)s * Hp + c];
+        M[(long)i * Hp + c] = alpha * t;
+      }
+    }
+  }
+  float s[3] = {0.f, 0.f, 0.f};
+  for (int e = e0 + lane; e < e1; e += 64) {
+    float xv = 0.f;
+    for (int t = 0; t < ntj; ++t) xv += xe_part[(long)t * xe_stride + e];
+    xe_out[e] = xv;
+    s[0] = fmaf(xv, rvec[3 * (long)e], s[0]);
+    s[1] = fmaf(xv, rvec[3 * (long)e + 1], s[1]);
+    s[2] = fmaf(xv, rvec[3 * (long)e + 2], s[2]);
+  }
+#pragma unroll
+  for (int d = 0; d < 3; ++d) {
+    float t = s[d];
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) t += __shfl_xor(t, o);
+    if (lane == 0) v_out[3 * (long)i + d] = v_in[3 * (long)i + d] + alpha * t;
   }
 }
 
@@ -441,7 +568,13 @@ static int32_t launch_fgemm_ad(hipStream_t st, const FGemmArgs& a) {
   const long gx = (a.nI / 8 + 7) / 8 * 8 * (long)(a.nJ / 4);
   HGNN_REQUIRE(gx <= 2147483647L, HGNN_ERR_OVERFLOW, "fragment GEMM: grid too large");
   ProfScope ps(a.tag, st);
-  k_fgemm_ad<<<dim3((unsigned)gx), 256, 0, st>>>(a);
+  if (a.seg_dst) {
+    HGNN_REQUIRE(a.seg_row_ptr && a.seg_wx && a.seg_M && a.seg_first && a.seg_last && a.seg_xe && a.seg_E <= (long)a.nI * 32,
+                 HGNN_ERR_NULLPTR, "fragment GEMM: incomplete per-atom sum arguments");
+    k_fgemm_ad<true><<<dim3((unsigned)gx), 256, 0, st>>>(a);
+  } else {
+    k_fgemm_ad<false><<<dim3((unsigned)gx), 256, 0, st>>>(a);
+  }
   HGNN_LAUNCH_CHECK("k_fgemm_ad");
   return HGNN_OK;
 }
@@ -893,69 +1026,6 @@ static dim3 elem_grid(int nrb, int Hp) {
   return dim3(Hp / 128, nrb < 1 ? 1 : (nrb < ELEM_MAX_BLOCKS ? nrb : ELEM_MAX_BLOCKS));
 }
 
-// ---------------------------------------------------------------------------------------------
-// per-atom reductions over T fragments (one wavefront per atom, lane (g, x) = lane half, column x of every block)
-// ---------------------------------------------------------------------------------------------
-// M_i = alpha sum_e silu(z2_e), v'_i = v_i + alpha sum_e (wx . silu(z2_e)) rvec_e over the rows e of atom i
-template <int NCB>
-__global__ void __launch_bounds__(256) k_seg_fwd_w(int N, const int32_t* __restrict__ row_ptr, const char* __restrict__ z2_T,
-                                                   const float* __restrict__ rvec, const float* __restrict__ wx, int H,
-                                                   float alpha, const float* __restrict__ v_in, float* __restrict__ M,
-                                                   float* __restrict__ v_out) {
-  const int lane = threadIdx.x & 63, g = lane >> 5, x = lane & 31;
-  const int i = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (i >= N) return;
-  const int e0 = row_ptr[i], e1 = row_ptr[i + 1];
-  float macc[NCB], wxv[NCB];
-#pragma unroll
-  for (int cb = 0; cb < NCB; ++cb) {
-    macc[cb] = 0.f;
-    wxv[cb] = cb * 32 + x < H ? wx[cb * 32 + x] : 0.f;
-  }
-  float s[3] = {0.f, 0.f, 0.f};
-  for (int rb16 = e0 >> 4; rb16 * 16 < e1; ++rb16) {
-    bool ok[8];
-    float rv[8][3];
-#pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      const int r = tset_row(rb16, g, u);
-      ok[u] = r >= e0 && r < e1;
-      const long rr = ok[u] ? r : 0;
-      rv[u][0] = rvec[3 * rr]; rv[u][1] = rvec[3 * rr + 1]; rv[u][2] = rvec[3 * rr + 2];
-    }
-    float y[8] = {};
-#pragma unroll
-    for (int cb = 0; cb < NCB; ++cb) {
-      float zz[8];
-      unpack8(*reinterpret_cast<const uint4*>(z2_T + (((long)rb16 * NCB + cb) * 64 + lane) * 16), zz);
-#pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        const float m = ok[u] ? silu_f(zz[u]) : 0.f;
-        macc[cb] += m;
-        y[u] = fmaf(wxv[cb], m, y[u]);
-      }
-    }
-#pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      s[0] = fmaf(y[u], rv[u][0], s[0]);
-      s[1] = fmaf(y[u], rv[u][1], s[1]);
-      s[2] = fmaf(y[u], rv[u][2], s[2]);
-    }
-  }
-#pragma unroll
-  for (int cb = 0; cb < NCB; ++cb) {
-    const float t = macc[cb] + __shfl_xor(macc[cb], 32);
-    if (g == 0) M[(long)i * (NCB * 32) + cb * 32 + x] = alpha * t;
-  }
-#pragma unroll
-  for (int d = 0; d < 3; ++d) {
-    float t = s[d];
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) t += __shfl_xor(t, o);
-    if (lane == 0) v_out[3 * (long)i + d] = v_in[3 * (long)i + d] + alpha * t;
-  }
-}
-
 // out[i][c] = sum over k in ptr[i] .. ptr[i+1] of X[perm[k]][c] (perm == null: X[k][c]), X bf16 row-major with pitch
 // Hp (one wavefront per atom, 16-byte pieces of a row per lane, two rows in flight)
 __global__ void __launch_bounds__(256) k_segsum_rows(int N, int Hp, const int32_t* __restrict__ ptr,
@@ -1012,26 +1082,6 @@ __global__ void __launch_bounds__(256) k_segsum_rows(int N, int Hp, const int32_
   }
 }
 
-static int32_t launch_seg_fwd_w(hipStream_t st, int Hp, int N, const int32_t* row_ptr, const char* z2_T, const float* rvec,
-                                const float* wx, int H, float alpha, const float* v_in, float* M, float* v_out) {
-  if (N <= 0) return HGNN_OK;
-  ProfScope ps(PT_SEG_FWD, st);
-  const unsigned grid = (unsigned)((N + 3) / 4);
-  switch (Hp / 32) {
-    case 4: k_seg_fwd_w<4><<<grid, 256, 0, st>>>(N, row_ptr, z2_T, rvec, wx, H, alpha, v_in, M, v_out); break;
-    case 8: k_seg_fwd_w<8><<<grid, 256, 0, st>>>(N, row_ptr, z2_T, rvec, wx, H, alpha, v_in, M, v_out); break;
-    case 12: k_seg_fwd_w<12><<<grid, 256, 0, st>>>(N, row_ptr, z2_T, rvec, wx, H, alpha, v_in, M, v_out); break;
-    case 16: k_seg_fwd_w<16><<<grid, 256, 0, st>>>(N, row_ptr, z2_T, rvec, wx, H, alpha, v_in, M, v_out); break;
-    case 20: k_seg_fwd_w<20><<<grid, 256, 0, st>>>(N, row_ptr, z2_T, rvec, wx, H, alpha, v_in, M, v_out); break;
-    case 24: k_seg_fwd_w<24><<<grid, 256, 0, st>>>(N, row_ptr, z2_T, rvec, wx, H, alpha, v_in, M, v_out); break;
-    case 28: k_seg_fwd_w<28><<<grid, 256, 0, st>>>(N, row_ptr, z2_T, rvec, wx, H, alpha, v_in, M, v_out); break;
-    case 32: k_seg_fwd_w<32><<<grid, 256, 0, st>>>(N, row_ptr, z2_T, rvec, wx, H, alpha, v_in, M, v_out); break;
-    default: return set_error(HGNN_ERR_BAD_SHAPE, "padded width %d is not supported", Hp);
-  }
-  HGNN_LAUNCH_CHECK("k_seg_fwd_w");
-  return HGNN_OK;
-}
-
 // g_attr[e][j] = sum_c g_z1[e][c] W1d[j][c], j < k <= 32: a product with one 32-column block of output. W1d^T sits in
 // LDS as B fragments (built once per workgroup), every wavefront multiplies 32-row blocks of the row-major bf16 g_z1,
 // whose 16-byte pieces are A fragments as they stand (lane (g, r): row r, columns 16 kb + 8 g ..).
@@ -1076,38 +1126,16 @@ __global__ void __launch_bounds__(256) k_gattr(int64_t E, int nrb, int H, int Hp
   }
 }
 
-// g_rvec_e = alpha x_e g_v'[dst_e] with x_e = wx . silu(z2_e)   (v'_i = v_i + alpha sum x_e rvec_e).
-// One wavefront per 16 edges: lane (g, x) reads the T fragments of the group, slot u is edge tset_row(rb16, g, u);
-// the eight sums over the 32 lanes of a half share one butterfly, each exchange halving the slots a lane still
-// carries (9 exchanges instead of 40); lane bits 4, 3, 2 of x end up naming the slot the lane holds.
-__global__ void __launch_bounds__(256) k_edge_grvec(int64_t E, int nrb16, int ncb, int H, const char* __restrict__ z2_T,
-                                                    const float* __restrict__ wx, const int32_t* __restrict__ dst,
-                                                    const float* __restrict__ g_v, float alpha,
-                                                    float* __restrict__ g_rvec) {
-  const int lane = threadIdx.x & 63, g = lane >> 5, x = lane & 31;
-  const int rb16 = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (rb16 >= nrb16) return;
-  float y[8] = {};
-#pragma unroll 4
-  for (int cb = 0; cb < ncb; ++cb) {   // ncb is a multiple of 4
-    const float w = cb * 32 + x < H ? wx[cb * 32 + x] : 0.f;
-    float zz[8];
-    unpack8(*reinterpret_cast<const uint4*>(z2_T + (((long)rb16 * ncb + cb) * 64 + lane) * 16), zz);
-#pragma unroll
-    for (int u = 0; u < 8; ++u) y[u] = fmaf(w, silu_f(zz[u]), y[u]);
-  }
-  const bool b4 = x & 16, b3 = x & 8, b2 = x & 4;
-  float a4[4], a2[2];
-#pragma unroll
-  for (int q = 0; q < 4; ++q) a4[q] = (b4 ? y[4 + q] : y[q]) + __shfl_xor(b4 ? y[q] : y[4 + q], 16);
-#pragma unroll
-  for (int q = 0; q < 2; ++q) a2[q] = (b3 ? a4[2 + q] : a4[q]) + __shfl_xor(b3 ? a4[q] : a4[2 + q], 8);
-  float t = (b2 ? a2[1] : a2[0]) + __shfl_xor(b2 ? a2[0] : a2[1], 4);
-  t += __shfl_xor(t, 2);
-  t += __shfl_xor(t, 1);
-  const long e = tset_row(rb16, g, (x >> 2) & 7);
-  const int c = x & 3;
-  if (c < 3 && e < E) g_rvec[3 * e + c] = alpha * t * g_v[3 * (size_t)dst[e] + c];
+// g_rvec_e = alpha x_e g_v'[dst_e]   (v'_i = v_i + alpha sum x_e rvec_e; x_e = wx . m_e kept by the forward pass)
+__global__ void k_edge_grvec(int64_t E, const int32_t* __restrict__ dst, const float* __restrict__ xe,
+                             const float* __restrict__ g_v, float alpha, float* __restrict__ g_rvec) {
+  const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= E) return;
+  const size_t i = (size_t)dst[e];
+  const float t = alpha * xe[e];
+  g_rvec[3 * e] = t * g_v[3 * i];
+  g_rvec[3 * e + 1] = t * g_v[3 * i + 1];
+  g_rvec[3 * e + 2] = t * g_v[3 * i + 2];
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1153,6 +1181,7 @@ struct WideSaved {
   float* z3;            // [Np, Hp]
   char* hM_T;           // [Np, 2 Hp] T fragments of [h ; M]     (operands of the reverse pass's weight gradients)
   char* a3_T;           // [Np, Hp] T fragments of silu(z3)
+  float* xe;            // [Ep] x_e = wx . m_e
   size_t bytes;
 };
 static WideSaved carve_saved_w(void* p, const WideDims& d) {
@@ -1166,6 +1195,7 @@ static WideSaved carve_saved_w(void* p, const WideDims& d) {
   s.z3 = c.take<float>((size_t)d.Np * d.Hp);
   s.hM_T = c.take<char>(d.node_frag_bytes(2));
   s.a3_T = c.take<char>(d.node_frag_bytes(1));
+  s.xe = c.take<float>((size_t)d.Ep + 4);
   s.bytes = c.used();
   return s;
 }
@@ -1184,6 +1214,9 @@ struct WideWs {
   char* gz2_R;              // [Ep, Hp]
   char* gz2_T;
   char* ga1_T;
+  float* seg_first;         // [Ep / 64, Hp] forward: sums of m over the part of a 64-row strip that belongs to an atom
+  float* seg_last;          //   that began before the strip / reaches past its end
+  float* xe_part;           // [ncb / 4, Ep] x_e per column tile
   float* cvec;              // [E]
   float* colpart;           // ELEM_MAX_BLOCKS x 2 x Hp (g_z2 kernel)
   float* colpart2;          // the same for the g_z1 kernel
@@ -1216,8 +1249,11 @@ static WideWs carve_ws_w(void* p, const WideDims& d) {
   w.cs_partial = c.take<float>(colsum_rows_partial_floats(d.N, d.Hp, 1));
   w.partial_floats = (size_t)24 * 2 * d.Hp * d.Hp;
   w.partial = c.take<float>(w.partial_floats);
-  w.partial_e_floats = (size_t)24 * d.Hp * d.Hp;
+  w.partial_e_floats = (size_t)(d.Hp <= 512 ? 96 : 24) * d.Hp * d.Hp;   // narrow outputs need more splits to fill the chip
   w.partial_e = c.take<float>(w.partial_e_floats);
+  w.seg_first = c.take<float>((size_t)(d.Ep / 64) * d.Hp);
+  w.seg_last = c.take<float>((size_t)(d.Ep / 64) * d.Hp);
+  w.xe_part = c.take<float>((size_t)(d.ncb / 4) * d.Ep);
   w.bytes = c.used();
   return w;
 }
@@ -1238,7 +1274,7 @@ static FGemmArgs nn_args(const char* A_R, int a_nkb, int nI, const unsigned shor
   return g;
 }
 
-constexpr int WIDE_MAX_SPLITS = 24;
+constexpr int WIDE_MAX_SPLITS = 256;   // (the partial buffers hold 24 splits of the widest outputs, more of narrow ones)
 int32_t launch_fwgrad(hipStream_t st, const FWgradArgs& a) {
   FGemmArgs g;
   g.A = a.A_T + (long)a.a_cb0 * 1024; g.a_si = 1; g.a_sk = a.a_ncb;
@@ -1250,12 +1286,14 @@ int32_t launch_fwgrad(hipStream_t st, const FWgradArgs& a) {
   // Long contractions over many rows (the per-edge gradient) take 256 x 128 tiles, which load a quarter fewer operand
   // bytes per flop (a last row tile may be half empty); everything else 128 x 128 tiles.
   // Enough splits for about three (two) workgroups per CU, as many as the partial buffer holds.
-  const bool big = !a.grp_ptr && a.nI >= 8 && a.rows >= 65536;   // (atom-level gradients measured the same either way)
-  const long tiles = big ? (long)((a.nI + 7) / 8) * (a.nJ / 4) : (long)(a.nI / 4) * (a.nJ / 4) * groups;
+  long cap = (long)(a.partial_floats / ((size_t)a.nI * 32 * a.nJ * 32 * groups));
+  if (cap > WIDE_MAX_SPLITS) cap = WIDE_MAX_SPLITS;
+  const long big_tiles = (long)((a.nI + 7) / 8) * (a.nJ / 4);
+  // (atom-level gradients measured the same either way; narrow outputs have too few large tiles to fill the chip)
+  const bool big = !a.grp_ptr && a.nI >= 8 && a.rows >= 65536 && big_tiles * cap >= 2L * num_cus();
+  const long tiles = big ? big_tiles : (long)(a.nI / 4) * (a.nJ / 4) * groups;
   long want = ((big ? 2L : 3L) * num_cus() + tiles - 1) / tiles;
-  const long cap = (long)(a.partial_floats / ((size_t)a.nI * 32 * a.nJ * 32 * groups));
   if (want > cap) want = cap;
-  if (want > WIDE_MAX_SPLITS) want = WIDE_MAX_SPLITS;
   want = want / 8 * 8;   // a multiple of 8: one XCD per residue (see k_fgemm)
   if (want < 8) want = 8;
   HGNN_REQUIRE(cap >= 8, HGNN_ERR_WORKSPACE_TOO_SMALL, "weight-gradient partials do not fit the workspace");
@@ -1373,9 +1411,18 @@ int32_t wide_layer_fwd(hipStream_t st, const WideLayerArgs& a) {
     FGemmArgs g = nn_args(s.a1_R, d.nkb, (int)(d.Ep / 32), w.packed + 2 * PP, d.ncb, PT_FRAG_GEMM_EDGE);
     g.T = s.z2_T; g.t_ncb = d.ncb;
     g.bias = W + o.b2; g.nbias = H;
+    // with the per-atom sums of m = silu(z2) and x_e = wx . m_e formed in the epilogue
+    g.seg_dst = a.dst; g.seg_row_ptr = a.row_ptr; g.seg_wx = W + o.wx; g.seg_H = H; g.seg_E = d.E; g.seg_alpha = a.alpha;
+    g.seg_M = s.M; g.seg_ldm = Hp; g.seg_first = w.seg_first; g.seg_last = w.seg_last; g.seg_ldp = Hp;
+    g.seg_xe = w.xe_part; g.seg_xe_stride = d.Ep;
     HGNN_TRY(launch_fgemm_rows_T(st, g));
   }
-  HGNN_TRY(launch_seg_fwd_w(st, Hp, d.N, a.row_ptr, s.z2_T, a.rvec, W + o.wx, H, a.alpha, a.v_in, s.M, a.v_out));
+  if (d.N > 0) {  // atoms whose edges span several strips, atoms without edges, v'
+    ProfScope ps(PT_SEG_FWD, st);
+    k_seg_fwd_fix<<<(unsigned)((d.N + 3) / 4), 256, 0, st>>>(d.N, Hp, d.ncb / 4, a.row_ptr, w.seg_first, w.seg_last,
+                                                            w.xe_part, d.Ep, a.rvec, a.alpha, a.v_in, s.M, a.v_out, s.xe);
+    HGNN_LAUNCH_CHECK("k_seg_fwd_fix");
+  }
   {  // M -> second half of the [h ; M] operand
     ToFragArgs t;
     t.X = s.M; t.ldx = Hp; t.M = d.N; t.Mp = d.Np; t.ncol = Hp; t.Cp = Hp;
@@ -1515,9 +1562,7 @@ int32_t wide_layer_bwd(hipStream_t st, const WideLayerArgs& a) {
   }
   if (a.g_rvec && d.E > 0) {
     ProfScope ps(PT_MISC, st);
-    const int nrb16 = (int)(d.Ep / 16);
-    k_edge_grvec<<<(unsigned)((nrb16 + 3) / 4), 256, 0, st>>>(d.E, nrb16, d.ncb, H, s.z2_T, W + o.wx, a.dst, a.g_v_out,
-                                                              a.alpha, a.g_rvec);
+    k_edge_grvec<<<(unsigned)((d.E + 255) / 256), 256, 0, st>>>(d.E, a.dst, s.xe, a.g_v_out, a.alpha, a.g_rvec);
     HGNN_LAUNCH_CHECK("k_edge_grvec");
   }
   // g_P, g_Q: per-atom sums of g_z1 over the destination-sorted and the source-sorted lists
