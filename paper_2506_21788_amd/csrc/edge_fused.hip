@@ -514,18 +514,30 @@ __global__ void __launch_bounds__(256, 2) k_edge_fwd(EdgeFwdArgs p, int ntiles) 
   }
 }
 
+// Workgroups of a kernel that one compute unit holds at once (registers and LDS decide). The persistent edge kernels
+// launch exactly that many per compute unit: a grid that is not a multiple of it runs a last, partly empty round
+// (four workgroups on a unit that holds three take as long as six).
+static int resident_per_cu(const void* kernel, size_t dyn_lds, int fallback) {
+  int n = 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kernel, 256, dyn_lds) != hipSuccess || n < 1) {
+    (void)hipGetLastError();
+    return fallback;
+  }
+  return n > 8 ? 8 : n;
+}
+
 template <int H, bool BF16>
 static int32_t launch_edge_fwd_t(hipStream_t st, const EdgeFwdArgs& a) {
   using C = ECfg<H, BF16>;
   const int64_t ntiles = (a.E + C::TM - 1) / C::TM;
   if (ntiles <= 0) return HGNN_OK;
-  static bool attr_set = false;
-  if (!attr_set) {
+  static int per_cu = 0;
+  if (!per_cu) {
     HGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_edge_fwd<H, BF16, true>),
                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)(C::LDS_BYTES + 6 * C::TM * 4)));
-    attr_set = true;
+    per_cu = resident_per_cu(reinterpret_cast<const void*>(&k_edge_fwd<H, BF16, true>), C::LDS_BYTES + 6 * C::TM * 4, 2);
   }
-  int64_t grid = (int64_t)num_cus() * 4;
+  int64_t grid = (int64_t)num_cus() * per_cu;
   if (grid > ntiles) grid = ntiles;
   ProfScope ps(PT_EDGE_FUSED_FWD, st);
   k_edge_fwd<H, BF16, true><<<dim3((unsigned)grid), 256, C::LDS_BYTES + 6 * C::TM * 4, st>>>(a, (int)ntiles);
@@ -1035,13 +1047,13 @@ template <int H, bool BF16>
 static int32_t launch_edge_bwd_t(hipStream_t st, const EdgeBwdArgs& a) {
   using C = ECfg<H, BF16>;
   const int64_t ntiles = (a.E + C::TM - 1) / C::TM;
-  static bool attr_set = false;
-  if (!attr_set) {
+  static int per_cu = 0;
+  if (!per_cu) {
     HGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_edge_bwd<H, BF16>),
                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)(C::LDS_BYTES + 8 * C::TM * 4)));
-    attr_set = true;
+    per_cu = resident_per_cu(reinterpret_cast<const void*>(&k_edge_bwd<H, BF16>), C::LDS_BYTES + 8 * C::TM * 4, 3);
   }
-  int64_t grid = (int64_t)num_cus() * 3;   // three workgroups are resident per CU
+  int64_t grid = (int64_t)num_cus() * per_cu;
   if (grid > EDGE_BWD_MAX_GRID) grid = EDGE_BWD_MAX_GRID;
   if (grid > ntiles) grid = ntiles;
   if (grid < 1) grid = 1;  // E == 0: one block writes zero partials
