@@ -83,7 +83,10 @@ def test_layer_other_modes_edge_counts(H, dtype, E):
                                    # enough edges for the 256 x 128 tiles of the per-edge weight gradient: a ragged
                                    # last row tile (Hp = 384: 8 + 4 blocks), a single whole one (Hp = 256 is served
                                    # by the fused kernels, so 200 -> 256), and two whole ones (512)
-                                   (320, 2000, 70001), (200, 1500, 66000), (512, 1800, 65536)])
+                                   (320, 2000, 70001), (200, 1500, 66000), (512, 1800, 65536),
+                                   # atoms whose edges span many 64-row strips of the forward per-atom sums (whole strips
+                                   # in the middle), next to atoms without edges
+                                   (384, 3, 1000), (866, 2, 300), (200, 40, 64), (200, 7, 65)])
 def test_layer_wide_widths(H, N, E):
     _run_layer(N=N, E=E, H=H, dtype="bf16", seed=H + E)
 
