@@ -584,22 +584,26 @@ static int32_t launch_fgemm_ad(hipStream_t st, const FGemmArgs& a) {
 // ---------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(256) k_pack_frag(PackFragArgs a) {
   const PackPart pt = a.part[blockIdx.y];
-  const long idx = (long)blockIdx.x * 256 + threadIdx.x;   // element of the part: [nb][kb][lane][u]
+  const long idx = (long)blockIdx.x * 256 + threadIdx.x;   // 16-byte piece of the part: [nb][kb][lane], 8 slots u each
   const int nkb = a.Kp / 16;
-  if (idx >= (long)a.Kp * a.Np) return;
-  const int u = idx & 7, lane = (idx >> 3) & 63;
-  const int f = (int)(idx >> 9);
+  if (idx >= (long)a.Kp * a.Np / 8) return;
+  const int lane = idx & 63;
+  const int f = (int)(idx >> 6);
   const int kb = f % nkb, nb = f / nkb;
-  const int k = kb * 16 + (lane >> 5) * 8 + u, n = nb * 32 + (lane & 31);
-  float v = 0.f;
-  if (k < a.K && n < a.Nn) v = a.src[blockIdx.z * a.src_grp_stride + pt.src_off + (long)k * pt.sk + (long)n * pt.sn];
-  a.dst[blockIdx.z * a.dst_grp_stride + pt.dst_off + (((long)(pt.nb0 + nb) * pt.nkb_total + pt.kb0 + kb) * 64 + lane) * 8 + u] =
-      (unsigned short)f2bf_bits(v);
+  const int k0 = kb * 16 + (lane >> 5) * 8, n = nb * 32 + (lane & 31);
+  const float* src = a.src + blockIdx.z * a.src_grp_stride + pt.src_off + (long)n * pt.sn;
+  float v[8];
+#pragma unroll
+  for (int u = 0; u < 8; ++u) v[u] = (k0 + u < a.K && n < a.Nn) ? src[(long)(k0 + u) * pt.sk] : 0.f;
+  uint4 w;
+  w.x = pack_bf16x2(v[0], v[1]); w.y = pack_bf16x2(v[2], v[3]); w.z = pack_bf16x2(v[4], v[5]); w.w = pack_bf16x2(v[6], v[7]);
+  *reinterpret_cast<uint4*>(a.dst + blockIdx.z * a.dst_grp_stride + pt.dst_off +
+                            (((long)(pt.nb0 + nb) * pt.nkb_total + pt.kb0 + kb) * 64 + lane) * 8) = w;
 }
 
 int32_t launch_pack_frag(hipStream_t st, const PackFragArgs& a) {
   ProfScope ps(PT_PACK, st);
-  k_pack_frag<<<dim3((unsigned)(((long)a.Kp * a.Np + 255) / 256), a.nparts, a.groups), 256, 0, st>>>(a);
+  k_pack_frag<<<dim3((unsigned)(((long)a.Kp * a.Np / 8 + 255) / 256), a.nparts, a.groups), 256, 0, st>>>(a);
   HGNN_LAUNCH_CHECK("k_pack_frag");
   return HGNN_OK;
 }
