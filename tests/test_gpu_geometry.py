@@ -92,7 +92,7 @@ def test_edge_rbf_reverse_and_cutoff(E, k):
 
 
 @pytest.mark.parametrize("N,E,H,k", [(300, 5000, 866, 8), (200, 3001, 256, 16), (64, 700, 333, 1), (100, 1500, 64, 4),
-                                     (50, 0, 128, 5)])
+                                     (50, 0, 128, 5), (100, 900, 1024, 2)])
 def test_layer_edge_gradients(N, E, H, k):
     """g_attr and g_rvec of the layer's reverse pass (the other outputs are covered by the layer tests)."""
     import torch
