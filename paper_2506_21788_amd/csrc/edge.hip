@@ -31,6 +31,26 @@ int32_t launch_fill_f32(hipStream_t st, float* dst, int64_t n, float v) {
   return HGNN_OK;
 }
 
+__global__ void k_edge_grvec(int64_t E, const int32_t* __restrict__ dst, const float* __restrict__ xe,
+                             const float* __restrict__ g_v, float alpha, float* __restrict__ g_rvec) {
+  const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= E) return;
+  const size_t i = (size_t)dst[e];
+  const float t = alpha * xe[e];
+  g_rvec[3 * e] = t * g_v[3 * i];
+  g_rvec[3 * e + 1] = t * g_v[3 * i + 1];
+  g_rvec[3 * e + 2] = t * g_v[3 * i + 2];
+}
+
+int32_t launch_edge_grvec(hipStream_t st, int64_t E, const int32_t* dst, const float* xe, const float* g_v, float alpha,
+                          float* g_rvec) {
+  if (E <= 0) return HGNN_OK;
+  ProfScope ps(PT_MISC, st);
+  k_edge_grvec<<<nblk64(E, 256), 256, 0, st>>>(E, dst, xe, g_v, alpha, g_rvec);
+  HGNN_LAUNCH_CHECK("k_edge_grvec");
+  return HGNN_OK;
+}
+
 // attr[e][j] = exp(-gamma (d - mu_j)^2) * fc(d),  d = sqrt(d2[e]),  mu_j = j rc / (k - 1),  gamma = ((k - 1) / rc)^2,
 // fc(d) = (cos(pi d / rc) + 1) / 2 inside the cutoff, 0 from the cutoff on   (float32, library expf / cosf)
 __global__ void k_edge_rbf(int64_t E, int k, const float* __restrict__ d2, float rc, float* __restrict__ attr) {

@@ -41,9 +41,10 @@ struct EdgeFwdArgs {
 int32_t launch_edge_fwd(hipStream_t st, int H, bool bf16, const EdgeFwdArgs& a);
 
 // M[i,:] = alpha * sum_{e in row i} silu(z2[e,:]);  v_out = v_in + alpha * sum (wx . silu(z2[e,:])) rvec[e,:]
+// xe (optional): [E] out, x_e = wx . m_e of every edge
 int32_t launch_seg_fwd_vm(hipStream_t st, int H, bool bf16, int N, const int32_t* row_ptr, const void* z2_vm,
                           const float* rvec, const float* wx, float alpha, const float* v_in, float* M,
-                          float* v_out);
+                          float* v_out, float* xe = nullptr);
 
 struct EdgeBwdArgs {
   int64_t E;
@@ -85,7 +86,9 @@ int32_t launch_wgrad_frag_recompute(hipStream_t st, int H, int64_t E, const int3
 
 // out[i, 0..H) (row pitch ldo) = sum over t in ptr[i]:ptr[i+1] of X[perm ? perm[t] : t, :], X v-major (bf16 or
 // fp32), accumulated in fp32
+// dot (optional): [E] out, dot[e] = sum_c wdot[c] X[e][c] for every edge of the list
 int32_t launch_segsum_vm(hipStream_t st, int H, bool bf16, int N, const int32_t* ptr, const int32_t* perm,
-                         const void* X_vm, float* out, int ldo, int tag);
+                         const void* X_vm, float* out, int ldo, int tag, const float* wdot = nullptr,
+                         float* dot = nullptr);
 
 }  // namespace hgnn

@@ -597,11 +597,14 @@ struct SegCols {
   }
 };
 
-template <int H, bool BF16>
+// XE: also keep x_e = wx . m_e of every edge (for the gradient with respect to the edge vectors); v' is then summed
+// from the x_e (another summation order than without XE)
+template <int H, bool BF16, bool XE>
 __global__ void __launch_bounds__(256)
 k_seg_fwd_vm(int N, const int32_t* __restrict__ row_ptr, const void* __restrict__ z2_vm,
              const float* __restrict__ rvec, const float* __restrict__ wx, float alpha,
-             const float* __restrict__ v_in, float* __restrict__ M, float* __restrict__ v_out) {
+             const float* __restrict__ v_in, float* __restrict__ M, float* __restrict__ v_out,
+             float* __restrict__ xe) {
   using S = SegCols<H, BF16, BF16 && H == 256>;
   constexpr int NV = S::NPASS * S::PER;
   const int i = __builtin_amdgcn_readfirstlane((int)(((size_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6));
@@ -609,6 +612,58 @@ k_seg_fwd_vm(int N, const int32_t* __restrict__ row_ptr, const void* __restrict_
   if (i >= N) return;
   const int hp = lane >> 5, x = lane & 31;
   const int e0 = row_ptr[i], e1 = row_ptr[i + 1];
+  if constexpr (XE) {
+    float acc[NV], wl[NV];
+#pragma unroll
+    for (int c = 0; c < S::NPASS; ++c)
+#pragma unroll
+      for (int k = 0; k < S::PER; ++k) {
+        acc[c * S::PER + k] = 0.f;
+        wl[c * S::PER + k] = wx[S::column(c, hp, x, k)];
+      }
+    float sx = 0.f, sy = 0.f, sz = 0.f;
+    constexpr int EPT = 4;
+    for (int e = e0; e < e1; e += EPT) {   // four edges per trip (clamped at the end of the row)
+      float z[EPT][NV], xs[EPT];
+#pragma unroll
+      for (int u = 0; u < EPT; ++u) {
+        const int ee = e + u < e1 ? e + u : e1 - 1;
+#pragma unroll
+        for (int c = 0; c < S::NPASS; ++c) S::fetch(z2_vm, (size_t)ee, c, hp, x, &z[u][c * S::PER]);
+      }
+#pragma unroll
+      for (int u = 0; u < EPT; ++u) {
+        const bool on = e + u < e1;
+        float t = 0.f;
+#pragma unroll
+        for (int c = 0; c < NV; ++c) {
+          const float m = on ? silu_f(z[u][c]) : 0.f;
+          acc[c] += m;
+          t = fmaf(wl[c], m, t);
+        }
+        xs[u] = wave_sum64(t);
+      }
+#pragma unroll
+      for (int u = 0; u < EPT; ++u)
+        if (e + u < e1) {
+          const size_t ee = (size_t)(e + u);
+          if (lane == 0) xe[ee] = xs[u];
+          sx = fmaf(xs[u], rvec[3 * ee], sx);
+          sy = fmaf(xs[u], rvec[3 * ee + 1], sy);
+          sz = fmaf(xs[u], rvec[3 * ee + 2], sz);
+        }
+    }
+#pragma unroll
+    for (int c = 0; c < S::NPASS; ++c)
+#pragma unroll
+      for (int k = 0; k < S::PER; ++k) M[(size_t)i * H + S::column(c, hp, x, k)] = alpha * acc[c * S::PER + k];
+    if (lane == 0) {
+      v_out[3 * (size_t)i] = v_in[3 * (size_t)i] + alpha * sx;
+      v_out[3 * (size_t)i + 1] = v_in[3 * (size_t)i + 1] + alpha * sy;
+      v_out[3 * (size_t)i + 2] = v_in[3 * (size_t)i + 2] + alpha * sz;
+    }
+    return;
+  }
   float acc[NV], tx[NV], ty[NV], tz[NV];
 #pragma unroll
   for (int c = 0; c < NV; ++c) acc[c] = tx[c] = ty[c] = tz[c] = 0.f;
@@ -673,15 +728,17 @@ k_seg_fwd_vm(int N, const int32_t* __restrict__ row_ptr, const void* __restrict_
 
 int32_t launch_seg_fwd_vm(hipStream_t st, int H, bool bf16, int N, const int32_t* row_ptr, const void* z2_vm,
                           const float* rvec, const float* wx, float alpha, const float* v_in, float* M,
-                          float* v_out) {
+                          float* v_out, float* xe) {
   if (N <= 0) return HGNN_OK;
   const unsigned grid = (unsigned)(((int64_t)N * 64 + 255) / 256);
   ProfScope ps(PT_SEG_FWD, st);
-#define HGNN_SEGF(HH, BB) k_seg_fwd_vm<HH, BB><<<grid, 256, 0, st>>>(N, row_ptr, z2_vm, rvec, wx, alpha, v_in, M, v_out)
+#define HGNN_SEGF(HH, BB)                                                                                        \
+  if (xe) k_seg_fwd_vm<HH, BB, true><<<grid, 256, 0, st>>>(N, row_ptr, z2_vm, rvec, wx, alpha, v_in, M, v_out, xe); \
+  else k_seg_fwd_vm<HH, BB, false><<<grid, 256, 0, st>>>(N, row_ptr, z2_vm, rvec, wx, alpha, v_in, M, v_out, xe)
   switch (H) {
-    case 64: if (bf16) HGNN_SEGF(64, true); else HGNN_SEGF(64, false); break;
-    case 128: if (bf16) HGNN_SEGF(128, true); else HGNN_SEGF(128, false); break;
-    case 256: if (bf16) HGNN_SEGF(256, true); else HGNN_SEGF(256, false); break;
+    case 64: if (bf16) { HGNN_SEGF(64, true); } else { HGNN_SEGF(64, false); } break;
+    case 128: if (bf16) { HGNN_SEGF(128, true); } else { HGNN_SEGF(128, false); } break;
+    case 256: if (bf16) { HGNN_SEGF(256, true); } else { HGNN_SEGF(256, false); } break;
     default: return set_error(HGNN_ERR_BAD_SHAPE, "H must be 64, 128 or 256");
   }
 #undef HGNN_SEGF
@@ -689,10 +746,12 @@ int32_t launch_seg_fwd_vm(hipStream_t st, int H, bool bf16, int N, const int32_t
   return HGNN_OK;
 }
 
-template <int H, bool BF16>
+// DOT: also dot[e] = sum_c wdot[c] X[e][c] for every edge of the list (the gradient with respect to d2 when X = g_z1
+// and wdot is the row of W1 that acts on d2)
+template <int H, bool BF16, bool DOT>
 __global__ void __launch_bounds__(256)
 k_segsum_vm(int N, const int32_t* __restrict__ ptr, const int32_t* __restrict__ perm, const void* __restrict__ X,
-            float* __restrict__ out, int ldo) {
+            float* __restrict__ out, int ldo, const float* __restrict__ wdot, float* __restrict__ dot) {
   using S = SegCols<H, BF16, BF16 && H == 256>;
   constexpr int NV = S::NPASS * S::PER;
   const int i = __builtin_amdgcn_readfirstlane((int)(((size_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6));
@@ -700,6 +759,45 @@ k_segsum_vm(int N, const int32_t* __restrict__ ptr, const int32_t* __restrict__ 
   if (i >= N) return;
   const int hp = lane >> 5, x = lane & 31;
   const int t0 = ptr[i], t1 = ptr[i + 1];
+  if constexpr (DOT) {
+    float acc[NV], wl[NV];
+#pragma unroll
+    for (int c = 0; c < S::NPASS; ++c)
+#pragma unroll
+      for (int k = 0; k < S::PER; ++k) {
+        acc[c * S::PER + k] = 0.f;
+        wl[c * S::PER + k] = wdot[S::column(c, hp, x, k)];
+      }
+    constexpr int EPT = 4;
+    for (int t = t0; t < t1; t += EPT) {   // four edges per trip (clamped at the end of the list)
+      float vv[EPT][NV];
+      size_t ee[EPT];
+#pragma unroll
+      for (int u = 0; u < EPT; ++u) {
+        const int tt = t + u < t1 ? t + u : t1 - 1;
+        ee[u] = perm ? (size_t)perm[tt] : (size_t)tt;
+#pragma unroll
+        for (int c = 0; c < S::NPASS; ++c) S::fetch(X, ee[u], c, hp, x, &vv[u][c * S::PER]);
+      }
+#pragma unroll
+      for (int u = 0; u < EPT; ++u) {
+        const bool on = t + u < t1;
+        float d = 0.f;
+#pragma unroll
+        for (int c = 0; c < NV; ++c) {
+          acc[c] += on ? vv[u][c] : 0.f;
+          d = fmaf(wl[c], vv[u][c], d);
+        }
+        d = wave_sum64(d);
+        if (on && lane == 0) dot[ee[u]] = d;
+      }
+    }
+#pragma unroll
+    for (int c = 0; c < S::NPASS; ++c)
+#pragma unroll
+      for (int k = 0; k < S::PER; ++k) out[(size_t)i * ldo + S::column(c, hp, x, k)] = acc[c * S::PER + k];
+    return;
+  }
   float acc[NV];
 #pragma unroll
   for (int c = 0; c < NV; ++c) acc[c] = 0.f;
@@ -734,15 +832,17 @@ k_segsum_vm(int N, const int32_t* __restrict__ ptr, const int32_t* __restrict__ 
 }
 
 int32_t launch_segsum_vm(hipStream_t st, int H, bool bf16, int N, const int32_t* ptr, const int32_t* perm,
-                         const void* X_vm, float* out, int ldo, int tag) {
+                         const void* X_vm, float* out, int ldo, int tag, const float* wdot, float* dot) {
   if (N <= 0) return HGNN_OK;
   const unsigned grid = (unsigned)(((int64_t)N * 64 + 255) / 256);
   ProfScope ps(tag, st);
-#define HGNN_SEGS(HH, BB) k_segsum_vm<HH, BB><<<grid, 256, 0, st>>>(N, ptr, perm, X_vm, out, ldo)
+#define HGNN_SEGS(HH, BB)                                                                            \
+  if (dot) k_segsum_vm<HH, BB, true><<<grid, 256, 0, st>>>(N, ptr, perm, X_vm, out, ldo, wdot, dot); \
+  else k_segsum_vm<HH, BB, false><<<grid, 256, 0, st>>>(N, ptr, perm, X_vm, out, ldo, wdot, dot)
   switch (H) {
-    case 64: if (bf16) HGNN_SEGS(64, true); else HGNN_SEGS(64, false); break;
-    case 128: if (bf16) HGNN_SEGS(128, true); else HGNN_SEGS(128, false); break;
-    case 256: if (bf16) HGNN_SEGS(256, true); else HGNN_SEGS(256, false); break;
+    case 64: if (bf16) { HGNN_SEGS(64, true); } else { HGNN_SEGS(64, false); } break;
+    case 128: if (bf16) { HGNN_SEGS(128, true); } else { HGNN_SEGS(128, false); } break;
+    case 256: if (bf16) { HGNN_SEGS(256, true); } else { HGNN_SEGS(256, false); } break;
     default: return set_error(HGNN_ERR_BAD_SHAPE, "H must be 64, 128 or 256");
   }
 #undef HGNN_SEGS

@@ -40,6 +40,7 @@ struct LayerSaved {
                 // reverse pass recomputes it
   float* M;     // [N,H]
   float* z3;    // [N,H]
+  float* xe;    // [E] x_e = wx . m_e (written only when the caller may ask for edge gradients)
   size_t bytes;
 };
 
@@ -52,6 +53,7 @@ static LayerSaved carve_saved(void* p, int N, int64_t E, int H, bool bf16) {
   s.a1_pk = edge_pairs(H, bf16) ? nullptr : c.take<char>(eb);
   s.M = c.take<float>((size_t)N * H);
   s.z3 = c.take<float>((size_t)N * H);
+  s.xe = c.take<float>((size_t)E + 4);
   s.bytes = c.used();
   return s;
 }
@@ -157,11 +159,11 @@ extern "C" int32_t hgnn_mp_layer_workspace_bytes(int32_t N, int64_t E, int32_t H
   return HGNN_OK;
 }
 
-extern "C" int32_t hgnn_mp_layer_fwd(void* stream, int32_t N, int64_t E, int32_t H, int32_t dtype, float alpha,
-                                     const int32_t* row_ptr, const int32_t* dst, const int32_t* col,
-                                     const float* d2, const float* rvec, const float* h_in, const float* v_in,
-                                     const float* W, float* h_out, float* v_out, void* saved, size_t saved_bytes,
-                                     void* ws, size_t ws_bytes) {
+// keep_xe: also keep x_e = wx . m_e per edge in the saved buffer (fused kernels only; the fragment path always does)
+static int32_t mp_layer_fwd_impl(void* stream, int32_t N, int64_t E, int32_t H, int32_t dtype, float alpha,
+                                 const int32_t* row_ptr, const int32_t* dst, const int32_t* col, const float* d2,
+                                 const float* rvec, const float* h_in, const float* v_in, const float* W, float* h_out,
+                                 float* v_out, void* saved, size_t saved_bytes, void* ws, size_t ws_bytes, bool keep_xe) {
   hipStream_t st = static_cast<hipStream_t>(stream);
   HGNN_TRY(check_layer_args(N, E, H, dtype));
   if (N == 0) return HGNN_OK;
@@ -225,7 +227,8 @@ extern "C" int32_t hgnn_mp_layer_fwd(void* stream, int32_t N, int64_t E, int32_t
     e.a1_pk = s.a1_pk; e.z2_vm = s.z2_vm;
     HGNN_TRY(launch_edge_fwd(st, H, bf16, e));
   }
-  HGNN_TRY(launch_seg_fwd_vm(st, H, bf16, N, row_ptr, s.z2_vm, rvec, W + o.wx, alpha, v_in, s.M, v_out));
+  HGNN_TRY(launch_seg_fwd_vm(st, H, bf16, N, row_ptr, s.z2_vm, rvec, W + o.wx, alpha, v_in, s.M, v_out,
+                             keep_xe ? s.xe : nullptr));
   {  // z3 = [h ; M] W3 + b3
     GemmArgs g;
     g.A[0] = h_in; g.lda[0] = H; g.A[1] = s.M; g.lda[1] = H; g.nkc = 2;
@@ -248,12 +251,23 @@ extern "C" int32_t hgnn_mp_layer_fwd(void* stream, int32_t N, int64_t E, int32_t
   return HGNN_OK;
 }
 
-extern "C" int32_t hgnn_mp_layer_bwd(void* stream, int32_t N, int64_t E, int32_t H, int32_t dtype, float alpha,
+extern "C" int32_t hgnn_mp_layer_fwd(void* stream, int32_t N, int64_t E, int32_t H, int32_t dtype, float alpha,
                                      const int32_t* row_ptr, const int32_t* dst, const int32_t* col,
-                                     const float* d2, const float* rvec, const int32_t* colT_ptr,
-                                     const int32_t* permT, const float* h_in, const float* W, const void* saved,
-                                     size_t saved_bytes, const float* g_h_out, const float* g_v_out,
-                                     float* g_h_in, float* g_v_in, float* gW, void* ws, size_t ws_bytes) {
+                                     const float* d2, const float* rvec, const float* h_in, const float* v_in,
+                                     const float* W, float* h_out, float* v_out, void* saved, size_t saved_bytes,
+                                     void* ws, size_t ws_bytes) {
+  return mp_layer_fwd_impl(stream, N, E, H, dtype, alpha, row_ptr, dst, col, d2, rvec, h_in, v_in, W, h_out, v_out, saved,
+                           saved_bytes, ws, ws_bytes, false);
+}
+
+// g_d2 / g_rvec (optional, fused kernels): gradient with respect to d2 and to the edge vectors; the forward pass must
+// have kept x_e
+static int32_t mp_layer_bwd_impl(void* stream, int32_t N, int64_t E, int32_t H, int32_t dtype, float alpha,
+                                 const int32_t* row_ptr, const int32_t* dst, const int32_t* col, const float* d2,
+                                 const float* rvec, const int32_t* colT_ptr, const int32_t* permT, const float* h_in,
+                                 const float* W, const void* saved, size_t saved_bytes, const float* g_h_out,
+                                 const float* g_v_out, float* g_h_in, float* g_v_in, float* gW, void* ws,
+                                 size_t ws_bytes, float* g_d2, float* g_rvec) {
   hipStream_t st = static_cast<hipStream_t>(stream);
   HGNN_TRY(check_layer_args(N, E, H, dtype));
   HGNN_REQUIRE(gW && W && ws, HGNN_ERR_NULLPTR, "mp_layer_bwd: null pointer");
@@ -369,7 +383,10 @@ extern "C" int32_t hgnn_mp_layer_bwd(void* stream, int32_t N, int64_t E, int32_t
                                          gW + o.W2));
   else
     HGNN_TRY(launch_wgrad_frag(sx, H, bf16, E, s.a1_pk, w.gz2_pk, w.partial2, gW + o.W2));
-  HGNN_TRY(launch_segsum_vm(st, H, bf16, N, row_ptr, nullptr, w.gz1_vm, w.g_PQ, 2 * H, PT_SEGSUM_DST));     // g_P
+  // g_P (and, on request, the gradient with respect to d2: the dot of every g_z1 row with the d2 row of W1)
+  HGNN_TRY(launch_segsum_vm(st, H, bf16, N, row_ptr, nullptr, w.gz1_vm, w.g_PQ, 2 * H, PT_SEGSUM_DST,
+                            W + o.W1 + 2 * HH, g_d2));
+  if (g_rvec) HGNN_TRY(launch_edge_grvec(st, E, dst, s.xe, g_v_out, alpha, g_rvec));
   HGNN_TRY(launch_segsum_vm(st, H, bf16, N, colT_ptr, permT, w.gz1_vm, w.g_PQ + H, 2 * H, PT_SEGSUM_SRC));  // g_Q
   HGNN_TRY(stream_after(sx, st, ss.ev[3]));
   {  // side: gW1a = h^T g_P ; gW1b = h^T g_Q ; gb1 = sum_i g_P_i (column sums of the first B operand)
@@ -397,8 +414,18 @@ extern "C" int32_t hgnn_mp_layer_bwd(void* stream, int32_t N, int64_t E, int32_t
   return HGNN_OK;
 }
 
+extern "C" int32_t hgnn_mp_layer_bwd(void* stream, int32_t N, int64_t E, int32_t H, int32_t dtype, float alpha,
+                                     const int32_t* row_ptr, const int32_t* dst, const int32_t* col,
+                                     const float* d2, const float* rvec, const int32_t* colT_ptr,
+                                     const int32_t* permT, const float* h_in, const float* W, const void* saved,
+                                     size_t saved_bytes, const float* g_h_out, const float* g_v_out,
+                                     float* g_h_in, float* g_v_in, float* gW, void* ws, size_t ws_bytes) {
+  return mp_layer_bwd_impl(stream, N, E, H, dtype, alpha, row_ptr, dst, col, d2, rvec, colT_ptr, permT, h_in, W, saved,
+                           saved_bytes, g_h_out, g_v_out, g_h_in, g_v_in, gW, ws, ws_bytes, nullptr, nullptr);
+}
+
 // ---------------------------------------------------------------------------------------------
-// the layer with k edge attributes in place of d2 (fragment path at every width)
+// the layer with k edge attributes in place of d2 (fragment path; one attribute at H = 64 / 128 / 256: the fused kernels)
 // ---------------------------------------------------------------------------------------------
 static int32_t check_attr_args(int N, int64_t E, int H, int k, int dtype) {
   HGNN_REQUIRE(N >= 0 && E >= 0, HGNN_ERR_BAD_SHAPE, "negative N or E");
@@ -406,14 +433,18 @@ static int32_t check_attr_args(int N, int64_t E, int H, int k, int dtype) {
   HGNN_REQUIRE(dtype == HGNN_F32 || dtype == HGNN_BF16, HGNN_ERR_BAD_SHAPE, "unknown dtype %d", dtype);
   HGNN_REQUIRE(H >= 1 && H <= 1024, HGNN_ERR_BAD_SHAPE, "H must lie in 1..1024 (got %d)", H);
   HGNN_REQUIRE(k >= 1 && k <= WIDE_MAX_ATTR, HGNN_ERR_BAD_SHAPE, "k must lie in 1..%d (got %d)", WIDE_MAX_ATTR, k);
-  HGNN_REQUIRE(dtype == HGNN_BF16, HGNN_ERR_UNIMPLEMENTED, "layers with edge attributes run with bf16 operands only");
+  HGNN_REQUIRE(dtype == HGNN_BF16 || (k == 1 && valid_H(H)), HGNN_ERR_UNIMPLEMENTED,
+               "layers with several edge attributes, or of a width other than 64, 128, 256, run with bf16 operands only");
   return HGNN_OK;
 }
+// one attribute (the squared edge length) at a width the fused kernels serve
+static bool attr_on_fused_kernels(int H, int k) { return k == 1 && valid_H(H); }
 
 extern "C" int32_t hgnn_mp_layer_attr_workspace_bytes(int32_t N, int64_t E, int32_t H, int32_t k, int32_t dtype,
                                                       size_t* ws_bytes_host, size_t* saved_bytes_host) {
   HGNN_TRY(check_attr_args(N, E, H, k, dtype));
   HGNN_REQUIRE(ws_bytes_host && saved_bytes_host, HGNN_ERR_NULLPTR, "null size pointer");
+  if (attr_on_fused_kernels(H, k)) return hgnn_mp_layer_workspace_bytes(N, E, H, dtype, ws_bytes_host, saved_bytes_host);
   wide_layer_sizes(N, E, H, k, ws_bytes_host, saved_bytes_host);
   return HGNN_OK;
 }
@@ -425,6 +456,9 @@ extern "C" int32_t hgnn_mp_layer_attr_fwd(void* stream, int32_t N, int64_t E, in
                                           void* ws, size_t ws_bytes) {
   hipStream_t st = static_cast<hipStream_t>(stream);
   HGNN_TRY(check_attr_args(N, E, H, k, dtype));
+  if (attr_on_fused_kernels(H, k))
+    return mp_layer_fwd_impl(stream, N, E, H, dtype, alpha, row_ptr, dst, col, attr, rvec, h_in, v_in, W, h_out, v_out,
+                             saved, saved_bytes, ws, ws_bytes, true);
   if (N == 0) return HGNN_OK;
   HGNN_REQUIRE(row_ptr && h_in && v_in && W && h_out && v_out && ws && saved, HGNN_ERR_NULLPTR, "mp_layer_attr_fwd: null pointer");
   HGNN_REQUIRE(E == 0 || (dst && col && attr && rvec), HGNN_ERR_NULLPTR, "mp_layer_attr_fwd: null edge array");
@@ -450,6 +484,9 @@ extern "C" int32_t hgnn_mp_layer_attr_bwd(void* stream, int32_t N, int64_t E, in
                                           size_t ws_bytes) {
   hipStream_t st = static_cast<hipStream_t>(stream);
   HGNN_TRY(check_attr_args(N, E, H, k, dtype));
+  if (attr_on_fused_kernels(H, k))
+    return mp_layer_bwd_impl(stream, N, E, H, dtype, alpha, row_ptr, dst, col, attr, rvec, colT_ptr, permT, h_in, W,
+                             saved, saved_bytes, g_h_out, g_v_out, g_h_in, g_v_in, gW, ws, ws_bytes, g_attr, g_rvec);
   HGNN_REQUIRE(gW && W && ws, HGNN_ERR_NULLPTR, "mp_layer_attr_bwd: null pointer");
   HGNN_REQUIRE(N == 0 || (row_ptr && colT_ptr && h_in && saved && g_h_out && g_v_out && g_h_in && g_v_in),
                HGNN_ERR_NULLPTR, "mp_layer_attr_bwd: null pointer");

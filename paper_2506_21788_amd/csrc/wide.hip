@@ -1130,18 +1130,6 @@ __global__ void __launch_bounds__(256) k_gattr(int64_t E, int nrb, int H, int Hp
   }
 }
 
-// g_rvec_e = alpha x_e g_v'[dst_e]   (v'_i = v_i + alpha sum x_e rvec_e; x_e = wx . m_e kept by the forward pass)
-__global__ void k_edge_grvec(int64_t E, const int32_t* __restrict__ dst, const float* __restrict__ xe,
-                             const float* __restrict__ g_v, float alpha, float* __restrict__ g_rvec) {
-  const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (e >= E) return;
-  const size_t i = (size_t)dst[e];
-  const float t = alpha * xe[e];
-  g_rvec[3 * e] = t * g_v[3 * i];
-  g_rvec[3 * e + 1] = t * g_v[3 * i + 1];
-  g_rvec[3 * e + 2] = t * g_v[3 * i + 2];
-}
-
 // ---------------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------------
@@ -1564,11 +1552,7 @@ int32_t wide_layer_bwd(hipStream_t st, const WideLayerArgs& a) {
     k_gattr<<<nwg, 256, (size_t)(Hp / 16) * 1024, st>>>(d.E, e.nrb, H, Hp, k, e.gz1_rm, e.w1d, a.g_attr);
     HGNN_LAUNCH_CHECK("k_gattr");
   }
-  if (a.g_rvec && d.E > 0) {
-    ProfScope ps(PT_MISC, st);
-    k_edge_grvec<<<(unsigned)((d.E + 255) / 256), 256, 0, st>>>(d.E, a.dst, s.xe, a.g_v_out, a.alpha, a.g_rvec);
-    HGNN_LAUNCH_CHECK("k_edge_grvec");
-  }
+  if (a.g_rvec) HGNN_TRY(launch_edge_grvec(st, d.E, a.dst, s.xe, a.g_v_out, a.alpha, a.g_rvec));
   // g_P, g_Q: per-atom sums of g_z1 over the destination-sorted and the source-sorted lists
   if (d.N > 0) {
     ProfScope ps(PT_SEGSUM_DST, st);

@@ -91,13 +91,18 @@ def test_edge_rbf_reverse_and_cutoff(E, k):
     assert relerr(got_g, oracle.edge_rbf_bwd(d2, k, rc, ga)) <= TOL["f32"]["grad"]
 
 
-@pytest.mark.parametrize("N,E,H,k", [(300, 5000, 866, 8), (200, 3001, 256, 16), (64, 700, 333, 1), (100, 1500, 64, 4),
-                                     (50, 0, 128, 5), (100, 900, 1024, 2)])
-def test_layer_edge_gradients(N, E, H, k):
-    """g_attr and g_rvec of the layer's reverse pass (the other outputs are covered by the layer tests)."""
+@pytest.mark.parametrize("N,E,H,k,dtype", [(300, 5000, 866, 8, "bf16"), (200, 3001, 256, 16, "bf16"),
+                                           (64, 700, 333, 1, "bf16"), (100, 1500, 64, 4, "bf16"), (50, 0, 128, 5, "bf16"),
+                                           (100, 900, 1024, 2, "bf16"),
+                                           # one attribute (the squared length) at the widths of the fused kernels
+                                           (200, 3001, 128, 1, "f32"), (300, 5003, 256, 1, "bf16"), (100, 1500, 64, 1, "f32"),
+                                           (150, 2000, 256, 1, "f32"), (90, 1100, 128, 1, "bf16"), (40, 0, 64, 1, "f32")])
+def test_layer_edge_gradients(N, E, H, k, dtype):
+    """g_attr and g_rvec of the layer's reverse pass, and with them every other output of the layer."""
     import torch
     from paper_2506_21788_amd import binding as B
-    say("layer edge gradients", N, E, H, k)
+    say("layer edge gradients", N, E, H, k, dtype)
+    dt = {"f32": B.F32, "bf16": B.BF16}[dtype]
     rc = 5.0
     rng = np.random.default_rng(N + E + H + k)
     row_ptr, dst, col, d2, rvec = _edges(rng, N, E)
@@ -110,7 +115,7 @@ def test_layer_edge_gradients(N, E, H, k):
     gh = rng.standard_normal((N, H)).astype(np.float32)
     gv = rng.standard_normal((N, 3)).astype(np.float32)
     alpha = 1.0 / max(1.0, E / N)
-    ws_b, saved_b = B.mp_layer_attr_workspace_bytes(N, E, H, k, B.BF16)
+    ws_b, saved_b = B.mp_layer_attr_workspace_bytes(N, E, H, k, dt)
     ws = torch.empty(ws_b, dtype=torch.uint8, device="cuda")
     saved = torch.empty(saved_b, dtype=torch.uint8, device="cuda")
     t = dict(row_ptr=_dev(row_ptr), dst=_dev(dst), col=_dev(col), attr=_dev(attr if E else np.zeros((1, k), np.float32)),
@@ -120,29 +125,36 @@ def test_layer_edge_gradients(N, E, H, k):
     g_h, g_v, gW = torch.empty_like(t["h"]), torch.empty_like(t["v"]), torch.empty_like(t["W"])
     g_attr = torch.full((max(E, 1), k), float("nan"), device="cuda")
     g_rvec = torch.full((max(E, 1), 3), float("nan"), device="cuda")
-    B.mp_layer_attr_fwd(N, E, H, k, B.BF16, alpha, t["row_ptr"], t["dst"], t["col"], t["attr"], t["rvec"], t["h"],
+    B.mp_layer_attr_fwd(N, E, H, k, dt, alpha, t["row_ptr"], t["dst"], t["col"], t["attr"], t["rvec"], t["h"],
                         t["v"], t["W"], h_out, v_out, saved, ws)
-    B.mp_layer_attr_bwd(N, E, H, k, B.BF16, alpha, t["row_ptr"], t["dst"], t["col"], t["attr"], t["rvec"], t["colT"],
+    B.mp_layer_attr_bwd(N, E, H, k, dt, alpha, t["row_ptr"], t["dst"], t["col"], t["attr"], t["rvec"], t["colT"],
                         t["permT"], t["h"], t["W"], saved, t["gh"], t["gv"], g_h, g_v, gW, ws, g_attr=g_attr,
                         g_rvec=g_rvec)
     torch.cuda.synchronize()
-    if E == 0:
-        return
-    _, _, cache = oracle.mp_layer_fwd(h, v, dst, col, d2, rvec, W.astype(np.float64), alpha, attr=attr)
-    _, _, _, want_ga, want_gr = oracle.mp_layer_bwd(cache, gh, gv, edge_grads=True)
-    got_ga, got_gr = g_attr.cpu().numpy(), g_rvec.cpu().numpy()
-    assert np.all(np.isfinite(got_ga)) and np.all(np.isfinite(got_gr))
-    errs = dict(g_attr=relerr(got_ga, want_ga), g_rvec=relerr(got_gr, want_gr))
-    say("  ", {n: f"{e:.1e}" for n, e in errs.items()})
+    ho, vo, cache = oracle.mp_layer_fwd(h, v, dst, col, d2, rvec, W.astype(np.float64), alpha, attr=attr)
+    gho, gvo, gWo, want_ga, want_gr = oracle.mp_layer_bwd(cache, gh, gv, edge_grads=True)
+    tol = TOL[dtype]
+    errs = dict(h=relerr(h_out.cpu().numpy(), ho), v=relerr(v_out.cpu().numpy(), vo))
+    gerrs = dict(g_h=relerr(g_h.cpu().numpy(), gho), g_v=relerr(g_v.cpu().numpy(), gvo))
+    got = oracle.unpack_layer(gW.cpu().numpy(), H, k)
+    for name, want in gWo.items():
+        gerrs["gW." + name] = relerr(got[name], want)
+    if E:
+        got_ga, got_gr = g_attr.cpu().numpy(), g_rvec.cpu().numpy()
+        assert np.all(np.isfinite(got_ga)) and np.all(np.isfinite(got_gr))
+        gerrs.update(g_attr=relerr(got_ga, want_ga), g_rvec=relerr(got_gr, want_gr))
+    say("  ", {n: f"{e:.1e}" for n, e in {**errs, **gerrs}.items()})
     for n, e in errs.items():
-        assert e <= TOL["bf16"]["grad"], (n, e)
+        assert e <= tol["fwd"], (n, e)
+    for n, e in gerrs.items():
+        assert e <= tol["grad"], (n, e)
 
 
 def _compare_geometry_step(P, label):
     import torch
     from hgnn_inputs import layer_field_slices
     hp = P["hp"]
-    tol = TOL["bf16"]
+    tol = TOL[hp["dtype"]]
     og = oracle_graph(P)
     hpth = gpu_hotpath(P)
     hpth.build_graph()
@@ -168,13 +180,16 @@ def _compare_geometry_step(P, label):
     return hpth, want
 
 
-@pytest.mark.parametrize("H,k,move", [(128, None, False), (128, 8, True), (866, None, True), (100, 16, False),
-                                      (256, 4, True)])
-def test_step_with_position_gradients(H, k, move):
-    say("step with position gradients", H, k, move)
+@pytest.mark.parametrize("H,k,move,dtype", [(128, None, False, "bf16"), (128, 8, True, "bf16"), (866, None, True, "bf16"),
+                                            (100, 16, False, "bf16"), (256, 4, True, "bf16"),
+                                            # the squared length alone at the fused kernels' widths: float32 operands too
+                                            (64, None, True, "f32"), (128, None, False, "f32"), (256, None, True, "f32"),
+                                            (256, None, True, "bf16")])
+def test_step_with_position_gradients(H, k, move, dtype):
+    say("step with position gradients", H, k, move, dtype)
     b = small_mixed_batch(21, n_mol=5, n_cry=4, S=3, mol_atoms=(3, 40), cry_atoms=(2, 30))
-    P = problem_from_batch(b, 4.5, H, 3, 3, "bf16", seed=H + (k or 0), rbf_k=k, move=move, pos_grad=True)
-    hpth, want = _compare_geometry_step(P, f"H={H} k={k} move={move}")
+    P = problem_from_batch(b, 4.5, H, 3, 3, dtype, seed=H + (k or 0), rbf_k=k, move=move, pos_grad=True)
+    hpth, want = _compare_geometry_step(P, f"H={H} k={k} move={move} {dtype}")
     # no net force on any structure
     g_pos = hpth.g_pos.cpu().numpy()
     scale = np.max(np.abs(g_pos))
