@@ -163,12 +163,15 @@ int32_t hgnn_mp_layer_bwd(void* stream, int32_t N, int64_t E, int32_t H, int32_t
  * hgnn_edge_rbf fills it with a radial basis of the edge length d = sqrt(d2) (the paper names no basis; this is the
  * usual Gaussian expansion with a smooth cutoff):
  *   attr[e][j] = exp(-gamma (d - mu_j)^2) * (cos(pi d / rc) + 1) / 2,  mu_j = j rc / (k-1),  gamma = ((k-1) / rc)^2
- * 2 <= k <= 16 there; the layer takes 1 <= k <= 16 and any attributes. 1 <= H <= 1024, dtype HGNN_BF16 only (HGNN_F32
- * -> UNIMPLEMENTED): at every width this variant runs through the fragment-GEMM kernels. Other arguments, side
- * stream, errors and aliasing rules as for hgnn_mp_layer_*. Only enqueue work.
+ * 2 <= k <= 16 there; the layer takes 1 <= k <= 16 and any attributes. 1 <= H <= 1024. With several attributes, or at
+ * a width other than 64 / 128 / 256, this variant runs through the fragment-GEMM kernels: dtype HGNN_BF16 only (HGNN_F32
+ * -> UNIMPLEMENTED). One attribute (k = 1, e.g. attr = d2) at H = 64 / 128 / 256 runs on the fused kernels of
+ * hgnn_mp_layer_* with either dtype, and differs from those calls only in the edge gradients below. Other arguments,
+ * side stream, errors and aliasing rules as for hgnn_mp_layer_*. Only enqueue work.
  * _bwd can also hand out what position gradients are made of (both optional, NULL = not wanted):
  *   g_attr [E,k]  gradient with respect to the edge attributes, g_attr[e][j] = sum_c g_z1[e][c] W1[2H + j][c]
  *   g_rvec [E,3]  gradient with respect to the edge vectors through v', g_rvec_e = alpha (wx . m_e) g_v_out[dst_e]
+ * (they need what hgnn_mp_layer_attr_fwd keeps in `saved`: pair _attr_bwd with _attr_fwd, not with hgnn_mp_layer_fwd).
  * ------------------------------------------------------------------------------------------- */
 int32_t hgnn_edge_rbf(void* stream, int64_t E, const float* d2 /*[E]*/, int32_t k, float rc,
                       float* attr /*out [E,k]*/);
