@@ -93,6 +93,17 @@ def test_host_side_argument_checks_need_no_gpu():
         ctypes.c_int32(10), ctypes.c_int32(2), ctypes.c_int32(128), ctypes.c_int32(Hh), ctypes.c_int32(2),
         ctypes.c_int32(dt), ctypes.byref(a), ctypes.byref(s))
     assert hw(64, 0) == code and hw(64, 1) == 0 and hw(2000, 1) == -2 and hw(128, 0) == 0
+    # layers with edge attributes: one attribute at 64 / 128 / 256 runs on the fused kernels in either operand type
+    # (same buffers as the plain layer); several attributes or other widths need bf16 operands
+    aw = lambda H, k, dt: lib.hgnn_mp_layer_attr_workspace_bytes(
+        ctypes.c_int32(10), ctypes.c_int64(50), ctypes.c_int32(H), ctypes.c_int32(k), ctypes.c_int32(dt),
+        ctypes.byref(a), ctypes.byref(s))
+    assert aw(128, 1, 0) == 0
+    a1, s1 = a.value, s.value
+    assert lib.hgnn_mp_layer_workspace_bytes(ctypes.c_int32(10), ctypes.c_int64(50), ctypes.c_int32(128), ctypes.c_int32(0),
+                                             ctypes.byref(a), ctypes.byref(s)) == 0 and (a.value, s.value) == (a1, s1)
+    assert aw(128, 2, 0) == code and aw(128, 2, 1) == 0 and aw(866, 1, 0) == code and aw(866, 1, 1) == 0
+    assert aw(128, 17, 1) == -2 and aw(128, 0, 1) == -2
     lib.hgnn_multihead_plan_ints.restype = ctypes.c_int64
     assert lib.hgnn_multihead_plan_ints(ctypes.c_int32(7), ctypes.c_int32(3), ctypes.c_int32(2)) >= 2 * 3 + 7 + 3 + 3
 
