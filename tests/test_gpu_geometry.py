@@ -230,3 +230,19 @@ def test_conservative_forces(move):
     errs = dict(energy=relerr(hpth.energy.cpu().numpy(), e), F=relerr(hpth.g_pos.cpu().numpy(), F))
     say("  ", {n: f"{v:.2e}" for n, v in errs.items()})
     assert errs["energy"] <= TOL["bf16"]["fwd"] and errs["F"] <= TOL["bf16"]["grad"]
+
+
+@pytest.mark.parametrize("name,move", [("cfg2", True), ("cfg3", False), ("cfg1", True)])
+def test_configs_with_position_gradients(name, move):
+    """Whole benchmark configs (config 2: 128 molecules, five sources, float32; config 3: periodic crystals with images
+    and self images, bf16; config 1: float32, H = 64) with position gradients, with and without moving atoms."""
+    from parity_util import problem_from_config
+    say("config with position gradients", name, move)
+    P = problem_from_config(name, move=move, pos_grad=True)
+    hpth, want = _compare_geometry_step(P, f"{name} move={move}")
+    b = P["batch"]
+    g_pos = hpth.g_pos.cpu().numpy()
+    scale = np.max(np.abs(g_pos))
+    for g in range(b.G):    # no net force on any structure, periodic ones included
+        lo, hi = int(b.graph_off[g]), int(b.graph_off[g + 1])
+        assert np.max(np.abs(g_pos[lo:hi].sum(axis=0))) <= 1e-4 * max(1.0, scale) * max(1, hi - lo)
