@@ -595,6 +595,27 @@ struct SegCols {
   __device__ static __forceinline__ int column(int c, int hp, int x, int k) {
     return PAIRS ? (2 * c + hp) * 64 + 32 * k + x : (2 * c + hp) * 32 + x;
   }
+  // The same fetch for an edge index that is uniform over the wavefront: everything that depends on the edge goes
+  // into the (scalar) base address, and a lane adds only its constant byte offset lane_off(c, hp, x) of pass c.
+  static constexpr unsigned ESZ = PAIRS ? 4u : (BF16 ? 2u : 4u);
+  static constexpr int NB = PAIRS ? NCB / 2 : NCB;
+  __device__ static __forceinline__ unsigned lane_off(int c, int hp, int x) {
+    return (unsigned)((2 * c + hp) * 1024 + x) * ESZ;
+  }
+  __device__ static __forceinline__ void fetch_u(const void* __restrict__ X, int e, unsigned loff, float* out) {
+    const int r = e & 31;
+    const size_t first = (((size_t)(e >> 5) * NB) * 16 + 4 * (r >> 3) + (r & 3)) * 64 + ((r >> 2) & 1) * 32;
+    const char* base = reinterpret_cast<const char*>(X) + first * ESZ;
+    if constexpr (PAIRS) {
+      const unsigned w = *reinterpret_cast<const unsigned*>(base + loff);
+      out[0] = __uint_as_float(w << 16);
+      out[1] = __uint_as_float(w & 0xffff0000u);
+    } else if constexpr (BF16) {
+      out[0] = bf_bits_to_f(*reinterpret_cast<const unsigned short*>(base + loff));
+    } else {
+      out[0] = *reinterpret_cast<const float*>(base + loff);
+    }
+  }
 };
 
 // XE: also keep x_e = wx . m_e of every edge (for the gradient with respect to the edge vectors); v' is then summed
@@ -612,6 +633,12 @@ k_seg_fwd_vm(int N, const int32_t* __restrict__ row_ptr, const void* __restrict_
   if (i >= N) return;
   const int hp = lane >> 5, x = lane & 31;
   const int e0 = row_ptr[i], e1 = row_ptr[i + 1];
+  unsigned loff[S::NPASS];   // kept as registers of their own: loads take a scalar base plus one of them
+#pragma unroll
+  for (int c = 0; c < S::NPASS; ++c) {
+    loff[c] = S::lane_off(c, hp, x);
+    asm volatile("" : "+v"(loff[c]));
+  }
   if constexpr (XE) {
     float acc[NV], wl[NV];
 #pragma unroll
@@ -629,7 +656,7 @@ k_seg_fwd_vm(int N, const int32_t* __restrict__ row_ptr, const void* __restrict_
       for (int u = 0; u < EPT; ++u) {
         const int ee = e + u < e1 ? e + u : e1 - 1;
 #pragma unroll
-        for (int c = 0; c < S::NPASS; ++c) S::fetch(z2_vm, (size_t)ee, c, hp, x, &z[u][c * S::PER]);
+        for (int c = 0; c < S::NPASS; ++c) S::fetch_u(z2_vm, ee, loff[c], &z[u][c * S::PER]);
       }
 #pragma unroll
       for (int u = 0; u < EPT; ++u) {
@@ -664,10 +691,20 @@ k_seg_fwd_vm(int N, const int32_t* __restrict__ row_ptr, const void* __restrict_
     }
     return;
   }
-  float acc[NV], tx[NV], ty[NV], tz[NV];
+  // x_e = wx . m_e stays spread over the lanes: a lane adds its share of x_e r_e for every edge and the lanes are
+  // summed once per atom
+  float acc[NV], wl[NV];
 #pragma unroll
-  for (int c = 0; c < NV; ++c) acc[c] = tx[c] = ty[c] = tz[c] = 0.f;
+  for (int c = 0; c < S::NPASS; ++c)
+#pragma unroll
+    for (int k = 0; k < S::PER; ++k) {
+      acc[c * S::PER + k] = 0.f;
+      wl[c * S::PER + k] = wx[S::column(c, hp, x, k)];
+    }
+  float sx = 0.f, sy = 0.f, sz = 0.f;
   // a row's edges are summed in list order; four edges per trip so that their loads are in flight together
+  // (asking for the next four while these are summed changes nothing: the kernel runs at the rate the memory
+  // system gives for this access pattern)
   constexpr int EPT = 4;
   int e = e0;
   for (; e + EPT <= e1; e += EPT) {
@@ -677,45 +714,42 @@ k_seg_fwd_vm(int N, const int32_t* __restrict__ row_ptr, const void* __restrict_
 #pragma unroll
       for (int k = 0; k < 3; ++k) r[u][k] = rvec[3 * (size_t)(e + u) + k];
 #pragma unroll
-      for (int c = 0; c < S::NPASS; ++c) S::fetch(z2_vm, (size_t)(e + u), c, hp, x, &z[u][c * S::PER]);
+      for (int c = 0; c < S::NPASS; ++c) S::fetch_u(z2_vm, e + u, loff[c], &z[u][c * S::PER]);
     }
 #pragma unroll
-    for (int u = 0; u < EPT; ++u)
+    for (int u = 0; u < EPT; ++u) {
+      float t = 0.f;
 #pragma unroll
       for (int c = 0; c < NV; ++c) {
         const float m = silu_f(z[u][c]);
         acc[c] += m;
-        tx[c] += m * r[u][0];
-        ty[c] += m * r[u][1];
-        tz[c] += m * r[u][2];
+        t = fmaf(wl[c], m, t);
       }
+      sx = fmaf(t, r[u][0], sx);
+      sy = fmaf(t, r[u][1], sy);
+      sz = fmaf(t, r[u][2], sz);
+    }
   }
   for (; e < e1; ++e) {
     const float rx = rvec[3 * (size_t)e], ry = rvec[3 * (size_t)e + 1], rz = rvec[3 * (size_t)e + 2];
     float z[NV];
 #pragma unroll
-    for (int c = 0; c < S::NPASS; ++c) S::fetch(z2_vm, (size_t)e, c, hp, x, &z[c * S::PER]);
+    for (int c = 0; c < S::NPASS; ++c) S::fetch_u(z2_vm, e, loff[c], &z[c * S::PER]);
+    float t = 0.f;
 #pragma unroll
     for (int c = 0; c < NV; ++c) {
       const float m = silu_f(z[c]);
       acc[c] += m;
-      tx[c] += m * rx;
-      ty[c] += m * ry;
-      tz[c] += m * rz;
+      t = fmaf(wl[c], m, t);
     }
+    sx = fmaf(t, rx, sx);
+    sy = fmaf(t, ry, sy);
+    sz = fmaf(t, rz, sz);
   }
-  float sx = 0.f, sy = 0.f, sz = 0.f;
 #pragma unroll
   for (int c = 0; c < S::NPASS; ++c)
 #pragma unroll
-    for (int k = 0; k < S::PER; ++k) {
-      const int n = S::column(c, hp, x, k);
-      const float w = wx[n];
-      M[(size_t)i * H + n] = alpha * acc[c * S::PER + k];
-      sx += w * tx[c * S::PER + k];
-      sy += w * ty[c * S::PER + k];
-      sz += w * tz[c * S::PER + k];
-    }
+    for (int k = 0; k < S::PER; ++k) M[(size_t)i * H + S::column(c, hp, x, k)] = alpha * acc[c * S::PER + k];
   sx = wave_sum64(sx);
   sy = wave_sum64(sy);
   sz = wave_sum64(sz);
