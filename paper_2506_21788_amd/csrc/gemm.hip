@@ -469,14 +469,19 @@ struct WgradCfg {
 };
 
 template <int H, bool BF16>
-__global__ void __launch_bounds__(256) k_wgrad(WgradArgs p, int nsplit, int rows_per_split) {
+__global__ void __launch_bounds__(256) k_wgrad(WgradArgs p, int nsplit, int rows_per_split, int ny) {
   using C = WgradCfg<H>;
   __shared__ __align__(16) float sA[WG_RC * C::STRIDE];
   __shared__ __align__(16) float sB[WG_RC * C::STRIDE];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wa = wave >> 1, wb = wave & 1;
-  const int split = blockIdx.x, grp = blockIdx.z;
-  int y = blockIdx.y;
+  // Workgroups are dealt to the 8 XCDs round-robin. The ny workgroups that read the same rows (one per output tile)
+  // take consecutive places on one XCD, so that they run at the same time behind the same L2 and the rows come
+  // from memory once: split s lives on XCD s % 8.
+  const int xcd = blockIdx.x & 7, place = blockIdx.x >> 3;
+  const int split = (place / ny) * 8 + xcd, grp = blockIdx.z;
+  if (split >= nsplit) return;   // uniform over the workgroup (the grid is padded to whole groups of 8 splits)
+  int y = place % ny;
   const int tb = y % C::TILES; y /= C::TILES;
   const int ta = y % C::TILES; y /= C::TILES;
   const int ib = y % p.nB;
@@ -622,21 +627,43 @@ size_t wgrad_partial_floats(int H, int64_t M, int nblocks, int S) {
   return (size_t)wgrad_splits(M) * nblocks * S * H * H;
 }
 
+// workgroups of k_wgrad that one CU holds at a time (asked once per variant)
+template <int H, bool BF16>
+static int wgrad_resident_wgs() {
+  static int n = 0;
+  if (n == 0) {
+    int occ = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, reinterpret_cast<const void*>(&k_wgrad<H, BF16>), 256, 0) !=
+            hipSuccess || occ < 1)
+      occ = 1;
+    n = occ;
+  }
+  return n;
+}
+
 template <int H, bool BF16>
 static int32_t launch_wgrad_t(hipStream_t st, const WgradArgs& a) {
   using C = WgradCfg<H>;
   const int nblk = a.nA * a.nB;
   const int groups = a.grp_ptr ? a.S : 1;
-  // as many splits as keep the launch within one round of resident workgroups (three per CU), never more than
-  // the workspace was sized for
+  const int ny = nblk * C::TILES * C::TILES;
+  // Splits: never more than the workspace was sized for; at most one round of resident workgroups (a second,
+  // partly filled round costs a whole one); and below that a whole number of workgroups per CU, so that no CU
+  // carries two while its neighbour carries one. Fewer splits also mean fewer partials to write and add up.
   int nsplit = wgrad_splits(a.M);
-  const long fit = 3L * num_cus() / ((long)nblk * C::TILES * C::TILES * groups);
-  if (nsplit > fit) nsplit = fit < 1 ? 1 : (int)fit;
+  const long per_split = (long)ny * groups;
+  const long one_round = (long)wgrad_resident_wgs<H, BF16>() * num_cus() / per_split;
+  if (nsplit > one_round) {
+    nsplit = one_round < 1 ? 1 : (int)one_round;
+  } else {
+    const long whole = nsplit * per_split / num_cus();
+    if (whole >= 1) nsplit = (int)(whole * num_cus() / per_split);
+  }
   int64_t rps = (a.M + nsplit - 1) / nsplit;
   rps = (rps + WG_RC - 1) / WG_RC * WG_RC;
   if (rps < WG_RC) rps = WG_RC;
   ProfScope ps(a.tag, st);
-  k_wgrad<H, BF16><<<dim3(nsplit, nblk * C::TILES * C::TILES, groups), 256, 0, st>>>(a, nsplit, (int)rps);
+  k_wgrad<H, BF16><<<dim3((unsigned)((nsplit + 7) / 8 * 8 * ny), 1, groups), 256, 0, st>>>(a, nsplit, (int)rps, ny);
   HGNN_LAUNCH_CHECK("k_wgrad");
   HGNN_TRY(launch_reduce_partials(st, a.partial, nsplit, nblk, (long)H * H, a.dest, groups, a.grp_dest_stride));
   if (a.colsum_partial) {
