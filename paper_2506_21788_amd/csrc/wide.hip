@@ -754,15 +754,31 @@ __global__ void __launch_bounds__(256) k_colsum_rows(ColsumRowsArgs a, int nspli
   int pos0 = 0, pad0 = 0, n = a.M;
   if (a.grp_ptr) group_range(a.grp_ptr, blockIdx.z, pos0, n, pad0);
   const int r0 = blockIdx.y * CS_ROWS;
-  const int r1 = r0 + CS_ROWS < n ? r0 + CS_ROWS : n;
   float s = 0.f;
-  for (int r = r0; r < r1; ++r) {
-    const long sr = a.row_idx ? a.row_idx[pos0 + r] : pad0 + r;
-    float v = a.X[sr * a.ldx + c];
-    if (a.mode == 1) v = silu_f(v);
-    else if (a.mode == 2) v *= dsilu_f(a.Z[sr * a.ldz + c]);
-    if (a.w) v *= a.w[sr];
-    s += v;
+  if (r0 < n) {   // uniform
+    // all rows of the partial are asked for before the first is used (rows past the end: the last one again, left
+    // out of the sum); summed in row order
+    long sr[CS_ROWS];
+    float xv[CS_ROWS], zv[CS_ROWS], wv[CS_ROWS];
+#pragma unroll
+    for (int u = 0; u < CS_ROWS; ++u) {
+      const int r = r0 + u < n ? r0 + u : n - 1;
+      sr[u] = a.row_idx ? a.row_idx[pos0 + r] : pad0 + r;
+    }
+#pragma unroll
+    for (int u = 0; u < CS_ROWS; ++u) {
+      xv[u] = a.X[sr[u] * a.ldx + c];
+      zv[u] = a.mode == 2 ? a.Z[sr[u] * a.ldz + c] : 0.f;
+      wv[u] = a.w ? a.w[sr[u]] : 1.f;
+    }
+#pragma unroll
+    for (int u = 0; u < CS_ROWS; ++u) {
+      float v = xv[u];
+      if (a.mode == 1) v = silu_f(v);
+      else if (a.mode == 2) v *= dsilu_f(zv[u]);
+      if (a.w) v *= wv[u];
+      if (r0 + u < n) s += v;
+    }
   }
   a.partial[((long)blockIdx.z * nsplit + blockIdx.y) * a.ncol + c] = s;
 }
