@@ -75,6 +75,16 @@ def test_layer_other_modes_edge_counts(H, dtype, E):
     _run_layer(N=300, E=E, H=H, dtype=dtype, seed=E)
 
 
+# Atom counts around the split rules of the atom-level weight gradients (about 256 rows per split, at most one round
+# of resident workgroups, whole workgroups per compute unit, a grid padded to groups of eight splits) and the row
+# tiles of the atom-level products; few edges, so that the atom-level kernels decide the outcome.
+@pytest.mark.parametrize("H,dtype,N", [(256, "bf16", 1), (256, "bf16", 255), (256, "bf16", 257), (256, "bf16", 2049),
+                                       (256, "bf16", 16385), (256, "bf16", 33001), (128, "f32", 9000),
+                                       (128, "bf16", 41000), (64, "f32", 70001), (256, "f32", 12345)])
+def test_layer_atom_counts(H, dtype, N):
+    _run_layer(N=N, E=3000, H=H, dtype=dtype, seed=N)
+
+
 # Widths other than 64 / 128 / 256 take the fragment-GEMM path (bf16 operands, width padded to a multiple of 128, rows
 # to 256): the paper's 866, widths on both sides of the padding steps, odd and small widths, edge counts around the
 # 16 / 32 / 256-row groups.
