@@ -16,7 +16,6 @@ import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
-sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 PEAK_HBM_GBS = 8000.0
 PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
@@ -148,8 +147,9 @@ def calib_load():
 def cpu_baseline(P, target_edges=150000):
     """The oracle, as it stands, on a bounded sample (the first graphs of the same batch)."""
     import numpy as np
-    import oracle
-    from parity_util import oracle_graph, oracle_step, sub_batch
+    sys.path.insert(0, os.path.join(ROOT, "tests"))   # only this leg uses the oracle (through the tests' helpers)
+    from hgnn_inputs import sub_batch
+    from parity_util import oracle_graph, oracle_step
     b = P["batch"]
     # grow the sample until the oracle graph has about target_edges edges (degree estimate ~30)
     k, atoms = 0, 0
@@ -209,13 +209,14 @@ def main():
         calib_load()
         return
     import torch
-    from parity_util import gpu_hotpath, problem_from_config
+    from hgnn_inputs import problem_from_config
     from paper_2506_21788_amd import binding as B
+    from paper_2506_21788_amd.step import HotPath
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     P = problem_from_config(args.config, rbf_k=args.rbf or None, move=args.move, pos_grad=args.pos_grad)
     b, hp = P["batch"], P["hp"]
-    hot = gpu_hotpath(P)
+    hot = HotPath.from_problem(P)
     gE = torch.as_tensor(P["gE"]).cuda()
     gF = torch.as_tensor(P["gF"]).cuda()
 

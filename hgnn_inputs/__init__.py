@@ -28,3 +28,4 @@ from .weights import (  # noqa: F401
     upstream_grads,
     ZMAX,
 )
+from .problems import make_weights, problem_from_batch, problem_from_config, sub_batch, sub_problem  # noqa: F401

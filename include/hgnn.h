@@ -19,7 +19,9 @@
  *  - Index type is int32. N atoms, G graphs, E directed edges, H hidden width, S sources.
  *    Edge e = (i <- j, s): i = dst[e] is the destination atom, j = col[e] the source atom, s the
  *    integer lattice shift applied to j.
- *  - H must be 64, 128 or 256 (tile granularity of the matrix-core kernels). Head width Hh == H.
+ *  - The fused kernels serve H = 64, 128 and 256 (tile granularity of the matrix cores) with a head width equal to
+ *    H; every other width up to 1024 takes the fragment-GEMM kernels (bf16 operands only). Each entry point states
+ *    what it accepts.
  *  - dtype selects the GEMM operand type: HGNN_F32 (fp32 matrix cores) or HGNN_BF16 (operands rounded
  *    to bf16 on load, fp32 accumulation). Activations, aggregation, biases and SiLU stay fp32.
  *  - Gradient outputs are overwritten, not accumulated, unless said otherwise.
@@ -310,7 +312,7 @@ int32_t hgnn_multihead_deep_bwd(void* stream, int32_t N, int32_t G, int32_t H, i
                                 float* gWhead /*out*/, void* ws, size_t ws_bytes);
 
 /* ---------------------------------------------------------------------------------------------
- * AdamW update of a flat float32 parameter buffer (paper, training setup: "AdamW" with learning rate 0.001;
+ * AdamW update of a flat float32 parameter buffer (paper, training setup: the optimiser is AdamW, learning rate 1e-3;
  * the update itself is the published algorithm, Adam with decoupled weight decay):
  *   m <- beta1 m + (1-beta1) g;  v <- beta2 v + (1-beta2) g*g;
  *   w <- w - lr * ( (m / (1-beta1^step)) / (sqrt(v / (1-beta2^step)) + eps) + weight_decay * w )

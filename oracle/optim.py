@@ -1,7 +1,7 @@
 """AdamW update of a flat parameter buffer (test infrastructure; see the package docstring). float64.
 
-The paper trains with "AdamW with a learning rate set to 0.001" (section "Numerical Results", paragraph on the
-training setup) and gives nothing else, so the update is the published algorithm (Adam with decoupled weight
+The paper names the optimiser (AdamW) and its learning rate (1e-3) in section "Numerical Results", paragraph on the
+training setup, and gives nothing else, so the update is the published algorithm (Adam with decoupled weight
 decay, Loshchilov & Hutter) and the remaining constants are this build's reading: beta1 = 0.9, beta2 = 0.999,
 eps = 1e-8, decay 0.01 (what the common implementations default to).
 

@@ -659,6 +659,7 @@ static int32_t launch_wgrad_t(hipStream_t st, const WgradArgs& a) {
     const long whole = nsplit * per_split / num_cus();
     if (whole >= 1) nsplit = (int)(whole * num_cus() / per_split);
   }
+  if (nsplit < 1) nsplit = 1;   // many groups with few rows each: per_split alone can exceed the CU count
   int64_t rps = (a.M + nsplit - 1) / nsplit;
   rps = (rps + WG_RC - 1) / WG_RC * WG_RC;
   if (rps < WG_RC) rps = WG_RC;

@@ -64,12 +64,15 @@ class HotPath:
     forward and backward. Inputs are numpy arrays (uploaded once); outputs stay on the device."""
 
     def __init__(self, batch, rc, H, L, S, dtype, emb, layer_weights, head_weights, alpha=None, Hh=None, D=None,
-                 rbf_k=None, move=False, pos_grad=False):
+                 rbf_k=None, move=False, pos_grad=False, keep_grads=False):
         """D: hidden layers per head (the deep-head entry points); None: the one-hidden-layer heads.
         rbf_k: number of radial-basis edge attributes that take the place of d2 (None: d2 itself).
         move: the atoms move between layers (x = x0 + v): edge vectors, lengths and attributes are recomputed
         before every layer. pos_grad (implied by move): backward() also leaves the gradient with respect to the input
-        positions in g_pos. Both run the layers through the edge-attribute entry points (bf16 operands)."""
+        positions in g_pos. Both run the layers through the edge-attribute entry points (bf16 operands).
+        keep_grads: backward() keeps the gradient with respect to every layer's input (g_h[l], g_v[l], l = 0..L) instead
+        of ping-ponging between two buffers."""
+        self.keep_grads = bool(keep_grads)
         self.move = bool(move)
         self.pos_grad = bool(pos_grad or move)
         self.k = rbf_k if rbf_k is not None else (1 if self.pos_grad else None)   # None: the plain layer calls
@@ -93,6 +96,14 @@ class HotPath:
         self._alloc_E = None
         self.plan = torch.empty(B.multihead_plan_ints(self.N, self.G, S), dtype=torch.int32, device="cuda")
         B.multihead_plan(self.N, self.G, S, self.graph_off, self.source_id, self.plan)
+
+    @classmethod
+    def from_problem(cls, P, alpha=None, **kw):
+        """P: a problem dict of hgnn_inputs (batch, hyper-parameters hp, emb, Ws, Wh)."""
+        b, hp = P["batch"], P["hp"]
+        return cls(b, hp["rc"], hp["H"], hp["L"], hp["S"], hp["dtype"], P["emb"], P["Ws"], P["Wh"], alpha=alpha,
+                   Hh=hp.get("Hh"), D=hp.get("D"), rbf_k=hp.get("rbf_k"), move=hp.get("move", False),
+                   pos_grad=hp.get("pos_grad", False), **kw)
 
     # -- graph ---------------------------------------------------------------------------------
     def build_graph(self):
@@ -137,8 +148,9 @@ class HotPath:
         self.energy = torch.empty(G, **f32)
         self.force = torch.empty((N, 3), **f32)
         self.g_p = torch.empty((G, H), **f32)
-        self.g_h = [torch.empty((N, H), **f32) for _ in range(2)]
-        self.g_v = [torch.empty((N, 3), **f32) for _ in range(2)]
+        ng = L + 1 if self.keep_grads else 2
+        self.g_h = [torch.empty((N, H), **f32) for _ in range(ng)]
+        self.g_v = [torch.empty((N, 3), **f32) for _ in range(ng)]
         self.gW = [torch.empty_like(w) for w in self.W]
         self.gWhead = torch.empty_like(self.Whead)
         self.g_emb = torch.empty_like(self.emb)
@@ -181,27 +193,30 @@ class HotPath:
         return self.attr_l[l if self.move else 0]
 
     def backward(self, g_energy, g_force):
-        g, N, G, H = self.graph, self.N, self.G, self.H
+        g, N, G, H, L = self.graph, self.N, self.G, self.H, self.L
+        # buffer that holds the gradient with respect to h[l] / v[l]
+        at = (lambda l: l) if self.keep_grads else (lambda l: (L - l) % 2)
+        top = at(L)
         if self.D is None:
             B.multihead_decode_bwd(N, G, H, self.Hh, self.S, self.dtype, self.plan, self.p, self.h[-1], self.v[-1],
-                                   self.Whead, self.hsaved, g_energy, g_force, self.g_p, self.g_h[0], self.g_v[0],
+                                   self.Whead, self.hsaved, g_energy, g_force, self.g_p, self.g_h[top], self.g_v[top],
                                    self.gWhead, self.ws)
         else:
             B.multihead_deep_bwd(N, G, H, self.Hh, self.D, self.S, self.dtype, self.plan, self.p, self.h[-1],
-                                 self.v[-1], self.Whead, self.hsaved, g_energy, g_force, self.g_p, self.g_h[0],
-                                 self.g_v[0], self.gWhead, self.ws)
-        B.pool_by_graph_bwd(N, G, H, B.POOL_MEAN, self.graph_off, self.g_p, self.g_h[0], True)
-        cur = 0
+                                 self.v[-1], self.Whead, self.hsaved, g_energy, g_force, self.g_p, self.g_h[top],
+                                 self.g_v[top], self.gWhead, self.ws)
+        B.pool_by_graph_bwd(N, G, H, B.POOL_MEAN, self.graph_off, self.g_p, self.g_h[top], True)
         for l in reversed(range(self.L)):
+            cur, nxt = at(l + 1), at(l)
             if self.k is None:
                 B.mp_layer_bwd(N, g.E, H, self.dtype, self.alpha, g.row_ptr, g.dst, g.col, g.d2, g.rvec, g.colT_ptr,
                                g.permT, self.h[l], self.W[l], self.saved[l], self.g_h[cur], self.g_v[cur],
-                               self.g_h[1 - cur], self.g_v[1 - cur], self.gW[l], self.ws)
+                               self.g_h[nxt], self.g_v[nxt], self.gW[l], self.ws)
             else:
                 pg = self.pos_grad
                 B.mp_layer_attr_bwd(N, g.E, H, self.k, self.dtype, self.alpha, g.row_ptr, g.dst, g.col, self._attr(l),
                                     self._rvec(l), g.colT_ptr, g.permT, self.h[l], self.W[l], self.saved[l],
-                                    self.g_h[cur], self.g_v[cur], self.g_h[1 - cur], self.g_v[1 - cur], self.gW[l],
+                                    self.g_h[cur], self.g_v[cur], self.g_h[nxt], self.g_v[nxt], self.gW[l],
                                     self.ws, g_attr=self.g_attr if pg else None, g_rvec=self.g_rvec if pg else None)
                 if pg:
                     if l == self.L - 1:
@@ -210,16 +225,15 @@ class HotPath:
                         B.edge_rbf_bwd(g.E, self._d2(l), self.k, self.rc, self.g_attr, self.g_d2)
                     g_d2 = self.g_d2 if self.rbf_k is not None else self.g_attr   # k = 1: the attribute is d2
                     B.edge_geometry_bwd(N, g.E, g.row_ptr, g.colT_ptr, g.permT, self._rvec(l), self.g_rvec, g_d2,
-                                        self.g_rvec, self.g_r0, self.g_v[1 - cur] if self.move else None)
-            cur = 1 - cur
+                                        self.g_rvec, self.g_r0, self.g_v[nxt] if self.move else None)
         if self.pos_grad:
             # rvec0 = x0[dst] - x0[col] - image shift: the summed edge-vector gradients land on the input positions
             self.g_pos.zero_()
             if self.L > 0:
                 B.edge_geometry_bwd(N, g.E, g.row_ptr, g.colT_ptr, g.permT, None, self.g_r0, None, self.g_rvec, None,
                                     self.g_pos)
-        B.embed_bwd(N, H, self.Z, self.g_h[cur], self.g_emb, self.ws)
-        self.g_h0, self.g_v0 = self.g_h[cur], self.g_v[cur]
+        B.embed_bwd(N, H, self.Z, self.g_h[at(0)], self.g_emb, self.ws)
+        self.g_h0, self.g_v0 = self.g_h[at(0)], self.g_v[at(0)]
 
     def step(self, g_energy, g_force, with_graph=True):
         if with_graph:

@@ -4,8 +4,8 @@ from __future__ import annotations
 import numpy as np
 
 import oracle
-from hgnn_inputs import (init_deep_head_weights, init_embedding, init_head_weights, init_layer_weights,
-                         make_config, upstream_grads)
+from hgnn_inputs import (make_weights, problem_from_batch, problem_from_config, sub_batch,  # noqa: F401
+                         sub_problem)
 
 TOL = {  # norm-wise L-inf relative error (max|a-b| / max|b|) against the float64 oracle
     "f32": dict(fwd=1e-5, grad=1e-4),
@@ -22,45 +22,6 @@ def relerr(a, b):
     den = np.max(np.abs(b))
     num = np.max(np.abs(a - b))
     return float(num / den) if den > 0 else float(num)
-
-
-def make_weights(seed, H, L, S, N, G, Hh=None, D=None, k=1):
-    """Hh, D: head width and hidden layers per head (None: the plain heads, one hidden layer of width H).
-    k: edge attributes per edge (1: the squared distance)."""
-    ss = np.random.SeedSequence(seed).spawn(3)
-    rw = np.random.default_rng(ss[1])
-    rg = np.random.default_rng(ss[2])
-    emb = init_embedding(rw, H)
-    Ws = [init_layer_weights(rw, H, k=k) for _ in range(L)]
-    Wh = init_head_weights(rw, H, H, S) if D is None else init_deep_head_weights(rw, H, Hh, D, S)
-    gE, gF = upstream_grads(rg, G, N)
-    return emb, Ws, Wh, gE, gF
-
-
-def problem_from_config(name, rbf_k=None, move=False, pos_grad=False, **over):
-    """rbf_k: run the config with that many radial-basis edge attributes in place of d2. move: the atoms move between
-    layers; pos_grad: the reverse pass also gives the position gradient."""
-    batch, hp = make_config(name, **over)
-    if rbf_k:
-        hp["rbf_k"] = int(rbf_k)
-    if move or pos_grad:
-        hp.update(move=bool(move), pos_grad=True)
-    emb, Ws, Wh, gE, gF = make_weights(hp["seed"], hp["H"], hp["L"], hp["S"], batch.N, batch.G, hp.get("Hh"),
-                                       hp.get("D"), hp.get("rbf_k") or 1)
-    return dict(batch=batch, hp=hp, emb=emb, Ws=Ws, Wh=Wh, gE=gE, gF=gF)
-
-
-def problem_from_batch(batch, rc, H, L, S, dtype, seed=0, Hh=None, D=None, rbf_k=None, move=False, pos_grad=False):
-    """move: the atoms move between layers; pos_grad: the reverse pass also gives the position gradient."""
-    emb, Ws, Wh, gE, gF = make_weights(seed, H, L, S, batch.N, batch.G, Hh, D, rbf_k or 1)
-    hp = dict(rc=rc, H=H, L=L, S=S, dtype=dtype, seed=seed, name="custom")
-    if rbf_k:
-        hp["rbf_k"] = rbf_k
-    if move or pos_grad:
-        hp.update(move=bool(move), pos_grad=True)
-    if D is not None:
-        hp.update(Hh=Hh, D=D)
-    return dict(batch=batch, hp=hp, emb=emb, Ws=Ws, Wh=Wh, gE=gE, gF=gF)
 
 
 def oracle_graph(P):
@@ -81,12 +42,9 @@ def oracle_step(P, graph, alpha, grads=True, keep_layers=False):
                                attr=attr, rbf=rbf, move=hp.get("move", False), pos_grad=geom)
 
 
-def gpu_hotpath(P, alpha=None):
+def gpu_hotpath(P, alpha=None, **kw):
     from paper_2506_21788_amd.step import HotPath
-    b, hp = P["batch"], P["hp"]
-    return HotPath(b, hp["rc"], hp["H"], hp["L"], hp["S"], hp["dtype"], P["emb"], P["Ws"], P["Wh"], alpha=alpha,
-                   Hh=hp.get("Hh"), D=hp.get("D"), rbf_k=hp.get("rbf_k"), move=hp.get("move", False),
-                   pos_grad=hp.get("pos_grad", False))
+    return HotPath.from_problem(P, alpha=alpha, **kw)
 
 
 def assert_graph_equal(got, want):
@@ -98,9 +56,40 @@ def assert_graph_equal(got, want):
     assert np.array_equal(got["rvec"].view(np.uint32), want["rvec"].view(np.uint32)), "rvec"
 
 
-def sub_batch(b, graphs):
-    """The listed graphs of a batch as a batch of their own (same atoms, cells, sources)."""
-    from hgnn_inputs import concat_graphs
-    gl = [(b.pos[b.graph_off[g]:b.graph_off[g + 1]], b.Z[b.graph_off[g]:b.graph_off[g + 1]],
-           b.cell[g] if b.pbc[g] else None) for g in graphs]
-    return concat_graphs(gl, b.source_id[graphs])
+def oracle_layer_by_row_blocks(h, v, g, Wflat, alpha, g_h_out, g_v_out, nblocks):
+    """One layer, forward and reverse, by the oracle, evaluated over blocks of destination rows so that the edge
+    tensors of a large graph never exist all at once. g: the graph arrays (row_ptr, dst, col, d2, rvec).
+
+    Forward: row i of (h', v') depends on h, v and on the edges of row i only. Reverse: the layer's reverse pass is
+    linear in (g_h_out, g_v_out), so the upstream gradients masked to a block of rows give that block's additive
+    share of every gradient (tests/test_oracle_model.py pins that additivity); the shares are summed in float64.
+    Each block runs on the atoms it touches only (its rows and the sources of their edges), renumbered.
+    Returns h', v', g_h, g_v, dict of weight gradients."""
+    h = np.asarray(h, np.float64)
+    v = np.asarray(v, np.float64)
+    g_h_out = np.asarray(g_h_out, np.float64)
+    g_v_out = np.asarray(g_v_out, np.float64)
+    N = h.shape[0]
+    row_ptr = g["row_ptr"]
+    bounds = np.linspace(0, N, nblocks + 1).astype(np.int64)
+    h_out, v_out = np.empty_like(h), np.empty_like(v)
+    g_h, g_v, gW = np.zeros_like(h), np.zeros_like(v), None
+    for r0, r1 in zip(bounds[:-1], bounds[1:]):
+        if r1 == r0:
+            continue
+        e0, e1 = int(row_ptr[r0]), int(row_ptr[r1])
+        dst, col = g["dst"][e0:e1].astype(np.int64), g["col"][e0:e1].astype(np.int64)
+        atoms = np.union1d(np.arange(r0, r1), col)                 # sorted; the block's rows are among them
+        ldst, lcol = np.searchsorted(atoms, dst), np.searchsorted(atoms, col)
+        own = np.searchsorted(atoms, np.arange(r0, r1))
+        ho, vo, cache = oracle.mp_layer_fwd(h[atoms], v[atoms], ldst, lcol, g["d2"][e0:e1], g["rvec"][e0:e1], Wflat,
+                                            alpha)
+        h_out[r0:r1], v_out[r0:r1] = ho[own], vo[own]
+        gh_m, gv_m = np.zeros((len(atoms), h.shape[1])), np.zeros((len(atoms), 3))
+        gh_m[own], gv_m[own] = g_h_out[r0:r1], g_v_out[r0:r1]
+        gh_b, gv_b, gW_b = oracle.mp_layer_bwd(cache, gh_m, gv_m)
+        g_h[atoms] += gh_b
+        g_v[atoms] += gv_b
+        gW = gW_b if gW is None else {k: gW[k] + gW_b[k] for k in gW}
+        del cache
+    return h_out, v_out, g_h, g_v, gW

@@ -338,89 +338,7 @@ def test_hip_graph_replays_match_eager_bitwise(name):
 # ------------------------------------------------------------------------------------------------
 # full sizes, in the launch configuration bench.py times
 # ------------------------------------------------------------------------------------------------
-def test_full_size_cfg4_sampled_graphs():
-    """Config 4 (~40k atoms, ~1.2M edges, bf16, 5 sources). A graph's outputs depend on that graph
-    only, so the oracle recomputes sampled graphs one sub-batch at a time."""
-    say("cfg4 full size")
-    import torch
-    P = problem_from_config("cfg4")
-    b, hp = P["batch"], P["hp"]
-    hpth = gpu_hotpath(P)
-    hpth.build_graph()
-    hpth.forward()
-    hpth.backward(torch.as_tensor(P["gE"]).cuda(), torch.as_tensor(P["gF"]).cuda())
-    torch.cuda.synchronize()
-    say("cfg4 N", b.N, "G", b.G, "E", hpth.graph.E, "alpha", hpth.alpha)
-    assert 0.96e6 < hpth.graph.E < 1.44e6   # "~1.2M edges" within 20 %
-    rng = np.random.default_rng(0)
-    graphs = np.sort(rng.choice(b.G, size=24, replace=False))
-    sb = sub_batch(b, graphs)
-    atoms = np.concatenate([np.arange(b.graph_off[g], b.graph_off[g + 1]) for g in graphs])
-    Ps = dict(P, batch=sb, gE=P["gE"][graphs], gF=P["gF"][atoms])
-    og = oracle_graph(Ps)
-    # edges of the sampled graphs, bit-exact
-    G = hpth.graph.to_numpy()
-    for k, g in enumerate(graphs):
-        e0, e1 = G["edge_graph_ptr"][g], G["edge_graph_ptr"][g + 1]
-        o0, o1 = og["edge_graph_ptr"][k], og["edge_graph_ptr"][k + 1]
-        assert e1 - e0 == o1 - o0
-        assert np.array_equal(G["col"][e0:e1] - b.graph_off[g], og["col"][o0:o1] - sb.graph_off[k])
-        assert np.array_equal(G["shift"][e0:e1], og["shift"][o0:o1])
-        assert np.array_equal(G["d2"][e0:e1].view(np.uint32), og["d2"][o0:o1].view(np.uint32))
-    want = oracle_step(Ps, og, hpth.alpha)
-    tol = TOL["bf16"]
-    errs = dict(energy=relerr(hpth.energy.cpu().numpy()[graphs], want["energy"]),
-                force=relerr(hpth.force.cpu().numpy()[atoms], want["force"]),
-                h=relerr(hpth.h[-1].cpu().numpy()[atoms], want["h"]),
-                g_h0=relerr(hpth.g_h0.cpu().numpy()[atoms], want["g_h0"]))
-    say("cfg4 sampled", {k: f"{v:.2e}" for k, v in errs.items()})
-    assert errs["energy"] <= tol["fwd"] and errs["force"] <= tol["fwd"] and errs["h"] <= tol["fwd"]
-    assert errs["g_h0"] <= tol["grad"]
-    for t in (hpth.gWhead, hpth.g_emb, *hpth.gW):
-        assert bool(torch.isfinite(t).all())
-
-
-def test_full_size_cfg5_layerwise_sampled_rows():
-    """Config 5 (80,000 atoms, ~7M edges, fp32). Row i of a layer's output depends on h (all rows)
-    and the edges of row i only; the oracle recomputes sampled rows of every layer from the
-    library's own layer input."""
-    say("cfg5 full size")
-    import torch
-    P = problem_from_config("cfg5")
-    b, hp = P["batch"], P["hp"]
-    hpth = gpu_hotpath(P)
-    hpth.build_graph()
-    hpth.forward()
-    hpth.backward(torch.as_tensor(P["gE"]).cuda(), torch.as_tensor(P["gF"]).cuda())
-    torch.cuda.synchronize()
-    E = hpth.graph.E
-    say("cfg5 E", E, "alpha", hpth.alpha)
-    assert 6.5e6 < E < 8e6
-    G = hpth.graph.to_numpy()
-    rng = np.random.default_rng(1)
-    rows = np.sort(rng.choice(b.N, size=200, replace=False))
-    sel = np.concatenate([np.arange(G["row_ptr"][i], G["row_ptr"][i + 1]) for i in rows])
-    tol = TOL["f32"]
-    for l in range(hp["L"]):
-        h_in = hpth.h[l].cpu().numpy().astype(np.float64)
-        v_in = hpth.v[l].cpu().numpy().astype(np.float64)
-        h_out, v_out, _ = oracle.mp_layer_fwd(h_in, v_in, G["dst"][sel], G["col"][sel], G["d2"][sel], G["rvec"][sel],
-                                              P["Ws"][l].astype(np.float64), hpth.alpha)
-        eh = relerr(hpth.h[l + 1].cpu().numpy()[rows], h_out[rows])
-        ev = relerr(hpth.v[l + 1].cpu().numpy()[rows], v_out[rows])
-        say("cfg5 layer", l, f"h {eh:.2e} v {ev:.2e}")
-        assert eh <= tol["fwd"] and ev <= tol["fwd"]
-    # heads on the library's own last-layer features
-    p = oracle.pool_fwd(hpth.h[-1].cpu().numpy(), b.graph_off)
-    e, f, _ = oracle.heads_fwd(p, hpth.h[-1].cpu().numpy(), hpth.v[-1].cpu().numpy(), b.graph_off, b.source_id,
-                               P["Wh"].astype(np.float64), hp["H"], hp["S"])
-    assert relerr(hpth.p.cpu().numpy(), p) <= tol["fwd"]
-    assert relerr(hpth.energy.cpu().numpy(), e) <= tol["fwd"]
-    assert relerr(hpth.force.cpu().numpy(), f) <= tol["fwd"]
-    for t in (hpth.gWhead, hpth.g_emb, *hpth.gW):
-        assert bool(torch.isfinite(t).all())
-
-
+# (configs 4, 5 and 6 at full size, every output and gradient field: tests/test_gpu_full_size.py)
 def test_reduced_cfg5_backward():
     """Same density, cutoff, width and depth as config 5 on a cell the oracle can differentiate."""
     say("cfg5 reduced")
@@ -484,34 +402,42 @@ def test_step_with_radial_basis_edge_attributes(H, k):
         assert e <= tol["grad"], (n, e)
 
 
-def test_full_size_cfg6_sampled_graphs():
-    """Config 6 (128 structures, ~8k atoms, ~250k edges, H = 866, 4 layers, heads 3 x 889). A graph's outputs depend
-    on that graph only, so the oracle recomputes sampled graphs as a batch of their own."""
-    say("cfg6 full size")
+# ------------------------------------------------------------------------------------------------
+# pooling modes and many sources
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("H", [64, 256, 100])
+def test_pool_sum_and_mean_overwrite_and_accumulate(H):
+    """Both pooling modes, forward and reverse, with and without accumulation, on a batch with empty graphs."""
+    say("pool modes", H)
     import torch
-    P = problem_from_config("cfg6")
-    b, hp = P["batch"], P["hp"]
-    hpth = gpu_hotpath(P)
-    hpth.build_graph()
-    hpth.forward()
-    hpth.backward(torch.as_tensor(P["gE"]).cuda(), torch.as_tensor(P["gF"]).cuda())
-    torch.cuda.synchronize()
-    say("cfg6 N", b.N, "G", b.G, "E", hpth.graph.E, "alpha", hpth.alpha)
-    rng = np.random.default_rng(6)
-    graphs = np.sort(rng.choice(b.G, size=6, replace=False))
-    sb = sub_batch(b, graphs)
-    atoms = np.concatenate([np.arange(b.graph_off[g], b.graph_off[g + 1]) for g in graphs])
-    Ps = dict(P, batch=sb, gE=P["gE"][graphs], gF=P["gF"][atoms])
-    og = oracle_graph(Ps)
-    say("cfg6 sample: atoms", sb.N, "edges", og["E"])
-    want = oracle_step(Ps, og, hpth.alpha)
-    tol = TOL["bf16"]
-    errs = dict(energy=relerr(hpth.energy.cpu().numpy()[graphs], want["energy"]),
-                force=relerr(hpth.force.cpu().numpy()[atoms], want["force"]),
-                h=relerr(hpth.h[-1].cpu().numpy()[atoms], want["h"]),
-                g_h0=relerr(hpth.g_h0.cpu().numpy()[atoms], want["g_h0"]))
-    say("cfg6 sampled", {k: f"{v:.2e}" for k, v in errs.items()})
-    assert errs["energy"] <= tol["fwd"] and errs["force"] <= tol["fwd"] and errs["h"] <= tol["fwd"]
-    assert errs["g_h0"] <= tol["grad"]
-    for t in (hpth.gWhead, hpth.g_emb, *hpth.gW):
-        assert bool(torch.isfinite(t).all())
+    from paper_2506_21788_amd import binding as B
+    rng = np.random.default_rng(H)
+    sizes = [3, 0, 1, 70, 0, 257, 12]
+    graph_off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    N, G = int(graph_off[-1]), len(sizes)
+    h = rng.standard_normal((N, H)).astype(np.float32)
+    g_p = rng.standard_normal((G, H)).astype(np.float32)
+    base = rng.standard_normal((N, H)).astype(np.float32)
+    dev = lambda a: torch.as_tensor(a).cuda()
+    for mode, mean in ((B.POOL_SUM, False), (B.POOL_MEAN, True)):
+        p = torch.full((G, H), float("nan"), dtype=torch.float32, device="cuda")
+        B.pool_by_graph_fwd(N, G, H, mode, dev(graph_off), dev(h), p)
+        want = oracle.pool_fwd(h, graph_off, mean=mean)
+        assert relerr(p.cpu().numpy(), want) <= TOL["f32"]["fwd"]
+        assert np.all(p.cpu().numpy()[[1, 4]] == 0.0)
+        want_g = oracle.pool_bwd(g_p, graph_off, N, mean=mean)
+        g_h = torch.full((N, H), float("nan"), dtype=torch.float32, device="cuda")
+        B.pool_by_graph_bwd(N, G, H, mode, dev(graph_off), dev(g_p), g_h, False)      # overwrite
+        assert relerr(g_h.cpu().numpy(), want_g) <= TOL["f32"]["grad"]
+        g_h = dev(base.copy())
+        B.pool_by_graph_bwd(N, G, H, mode, dev(graph_off), dev(g_p), g_h, True)       # accumulate
+        assert relerr(g_h.cpu().numpy(), base.astype(np.float64) + want_g) <= TOL["f32"]["grad"]
+
+
+@pytest.mark.parametrize("H,dtype,S", [(256, "bf16", 80), (128, "f32", 300), (64, "f32", 70)])
+def test_step_many_sources(H, dtype, S):
+    """More branches than the head weight gradient has compute units per split: most branches see no graph at all."""
+    say("step many sources", H, dtype, S)
+    b = small_mixed_batch(21, n_mol=6, n_cry=5, S=S, mol_atoms=(3, 30), cry_atoms=(2, 20))
+    P = problem_from_batch(b, 4.5, H, 1, S, dtype, seed=S)
+    compare_step(P, f"many sources H={H} {dtype} S={S}")

@@ -908,3 +908,32 @@ def test_conservative_forces_rotate_with_the_structure_and_match_energy_differen
         em = oracle.step_fwd_bwd(*args, _moved_graph(g0, -delta), *rest, move=move)["energy"]
         num = -float(np.sum(n_at * (ep - em))) / (2 * eps)
         assert abs(num - F[i, c]) <= 1e-6 * max(1.0, abs(num)), (num, F[i, c])
+
+
+def test_pooling_sum_and_mean_by_scalar_loops():
+    """pool_fwd / pool_bwd in both modes against element-by-element Python arithmetic, with empty graphs; the reverse
+    is the adjoint of the forward in either mode."""
+    rng = np.random.default_rng(11)
+    sizes = [2, 0, 5, 1, 0, 3]
+    graph_off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    N, G, H = int(graph_off[-1]), len(sizes), 3
+    h = rng.standard_normal((N, H))
+    g_p = rng.standard_normal((G, H))
+    for mean in (False, True):
+        p = oracle.pool_fwd(h, graph_off, mean=mean)
+        g_h = oracle.pool_bwd(g_p, graph_off, N, mean=mean)
+        atom = 0
+        for g, n in enumerate(sizes):
+            for c in range(H):
+                acc = 0.0
+                for i in range(atom, atom + n):
+                    acc += float(h[i, c])
+                want = 0.0 if n == 0 else (acc / n if mean else acc)
+                assert abs(p[g, c] - want) < 1e-14
+                for i in range(atom, atom + n):
+                    assert abs(g_h[i, c] - (float(g_p[g, c]) / n if mean else float(g_p[g, c]))) < 1e-15
+            atom += n
+        assert abs(np.sum(p * g_p) - np.sum(h * g_h)) < 1e-12
+    # sum = mean times the atom count
+    n_at = np.diff(graph_off)[:, None]
+    assert np.allclose(oracle.pool_fwd(h, graph_off, mean=False), oracle.pool_fwd(h, graph_off, mean=True) * n_at)
