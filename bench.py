@@ -99,51 +99,6 @@ def calib_copy():
     print(json.dumps({"calib_copy_bytes_read": n * 4, "calib_copy_bytes_written": n * 4, "copies": 5}))
 
 
-def calib_mfma():
-    """What the matrix pipes sustain on register-only work (context for the published peaks)."""
-    import torch
-    from paper_2506_21788_amd import binding as B
-    sink = torch.zeros(1, dtype=torch.float32, device="cuda")
-    out = {}
-    for name, dt in (("bf16", B.BF16), ("f32", B.F32)):
-        B.mfma_probe(dt, 2048, 256, sink)
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        flops = B.mfma_probe(dt, 2048, 8192, sink)
-        e1.record()
-        torch.cuda.synchronize()
-        out[name] = {"TFLOP_per_s": flops / (e0.elapsed_time(e1) * 1e-3) / 1e12, "published_peak": PEAK_TFLOPS[name]}
-    print(json.dumps({"calib_mfma": out}))
-
-
-def calib_load():
-    """What the vector memory path and the LDS deliver with 16-byte loads per lane (context for the operand traffic of
-    the matrix kernels): bytes per clock and compute unit at the 2.4 GHz the peaks are quoted at."""
-    import torch
-    from paper_2506_21788_amd import binding as B
-    sink = torch.zeros(4, dtype=torch.int32, device="cuda")
-    cases = {"l1_shared_16KiB": (0, -16, 1 << 21), "l2_buffer_2MiB": (0, 0, 1 << 21), "l2_buffer_16MiB": (0, 0, 1 << 24),
-             "mall_buffer_128MiB": (0, 0, 1 << 27), "hbm_buffer_4GiB": (0, 0, 1 << 32), "lds": (1, 0, 0),
-             "to_lds_l2_buffer_16MiB": (2, 0, 1 << 24), "to_lds_hbm_buffer_4GiB": (2, 0, 1 << 32)}
-    out = {}
-    for name, (kind, window, nbytes) in cases.items():
-        buf = torch.arange(nbytes // 4, dtype=torch.int32, device="cuda") if nbytes else None
-        B.load_probe(kind, 2048, 64, window, buf, sink)
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        moved = B.load_probe(kind, 2048, 2048, window, buf, sink)
-        e1.record()
-        torch.cuda.synchronize()
-        s = e0.elapsed_time(e1) * 1e-3
-        out[name] = {"TB_per_s": moved / s / 1e12, "bytes_per_clk_per_cu_at_2.4GHz": moved / s / 256 / 2.4e9}
-        if kind == 2:
-            out[name]["mismatching_lanes"] = int(sink[1].item())
-        del buf
-    print(json.dumps({"calib_load": out}))
-
-
 def cpu_baseline(P, target_edges=150000):
     """The oracle, as it stands, on a bounded sample (the first graphs of the same batch)."""
     import numpy as np
@@ -191,8 +146,6 @@ def main():
     ap.add_argument("--move", action="store_true",
                     help="the atoms move between layers (edge geometry recomputed per layer; implies --pos-grad)")
     ap.add_argument("--calib-copy", action="store_true", help="only run a 1 GiB copy kernel (counter calibration)")
-    ap.add_argument("--calib-mfma", action="store_true", help="only run the matrix-core rate probe")
-    ap.add_argument("--calib-load", action="store_true", help="only run the load-path rate probe (L1 / L2 / HBM / LDS)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; no figure at several GPUs exists (--gpus 1 only)",
@@ -201,12 +154,6 @@ def main():
 
     if args.calib_copy:
         calib_copy()
-        return
-    if args.calib_mfma:
-        calib_mfma()
-        return
-    if args.calib_load:
-        calib_load()
         return
     import torch
     from hgnn_inputs import problem_from_config

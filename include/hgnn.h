@@ -337,25 +337,6 @@ int32_t hgnn_profile_num_tags(void);
 const char* hgnn_profile_tag_name(int32_t tag);
 int32_t hgnn_profile_read(int32_t tag, int64_t* launches_host, double* total_ms_host);
 
-/* Matrix-core rate probe (instrumentation): launches `workgroups` x 4 wavefronts that each issue 4 * iters
- * register-only 32x32 matrix-core instructions (dtype HGNN_BF16: 32x32x16 bf16; HGNN_F32: 32x32x2 fp32) and
- * returns the number of floating-point operations that launch performs (0 on a bad argument or launch failure).
- * The caller times it; `sink` is one device float that is never written in practice. Only enqueues work. */
-int64_t hgnn_mfma_probe(void* stream, int32_t dtype, int32_t workgroups, int32_t iters, float* sink);
-
-/* Load-path rate probe (instrumentation): `workgroups` x 4 wavefronts each issue 8 * iters loads of 1 KiB (16 bytes
- * per lane, eight in flight) and the call returns the bytes that launch loads (0 on a bad argument or launch failure).
- * kind 0: from the device buffer buf (buf_bytes, a multiple of 1 KiB, at least 8 KiB); wavefront w walks cyclically
- *         the chunks w * window .. + window - 1 (window_chunks >= 8), its equal share of the buffer (window_chunks == 0:
- *         a buffer far larger than the caches streams from HBM, one of a few MB stays in the L2), or the first
- *         -window_chunks chunks, the same for every wavefront (window_chunks <= -8: they stay in the L1);
- * kind 1: from a 32 KiB LDS array (buf unused);
- * kind 2: as kind 0 with window_chunks == 0, but from memory straight into the LDS without passing through registers;
- *         the first rounds compare what landed with plain loads and add the number of mismatching lanes to sink[1].
- * The caller times it; `sink` is two device words, the first never written in practice. Only enqueues work. */
-int64_t hgnn_load_probe(void* stream, int32_t kind, int32_t workgroups, int32_t iters, int64_t window_chunks,
-                        const void* buf /*device*/, int64_t buf_bytes, void* sink /*device*/);
-
 #ifdef __cplusplus
 }
 #endif

@@ -27,7 +27,7 @@ EXPORTS = [
     "hgnn_multihead_plan_ints", "hgnn_multihead_plan",
     "hgnn_multihead_decode_workspace_bytes", "hgnn_multihead_decode_fwd", "hgnn_multihead_decode_bwd",
     "hgnn_multihead_deep_workspace_bytes", "hgnn_multihead_deep_fwd", "hgnn_multihead_deep_bwd",
-    "hgnn_adamw_step", "hgnn_mfma_probe", "hgnn_load_probe",
+    "hgnn_adamw_step",
     "hgnn_profile_begin", "hgnn_profile_end", "hgnn_profile_num_tags", "hgnn_profile_tag_name",
     "hgnn_profile_read",
 ]
@@ -305,21 +305,6 @@ def profile_tag_name(tag):
 def adamw_step(w, g, m, v, step, lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01):
     """In-place AdamW update of the flat float32 device tensor w (moments m, v; gradient g); step counts from 1."""
     _check(_adamw(_stream(), w.numel(), _p(w), _p(g), _p(m), _p(v), step, lr, beta1, beta2, eps, weight_decay))
-
-
-def mfma_probe(dtype, workgroups, iters, sink):
-    """Launch the matrix-core rate probe; returns the floating-point operations of the launch."""
-    _lib.hgnn_mfma_probe.restype = C.c_int64
-    return int(_lib.hgnn_mfma_probe(_stream(), C.c_int32(dtype), C.c_int32(workgroups), C.c_int32(iters), _p(sink)))
-
-
-def load_probe(kind, workgroups, iters, window_chunks, buf, sink):
-    """Launch the load-path rate probe; returns the bytes the launch loads."""
-    _lib.hgnn_load_probe.restype = C.c_int64
-    return int(_lib.hgnn_load_probe(_stream(), C.c_int32(kind), C.c_int32(workgroups), C.c_int32(iters),
-                                    C.c_int64(window_chunks), _p(buf), C.c_int64(0 if buf is None else buf.numel() * buf.element_size()),
-                                    _p(sink)))
-
 
 def profile_begin(tag_mask):
     _check(_prof_begin(tag_mask))
