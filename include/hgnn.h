@@ -111,6 +111,17 @@ int32_t hgnn_embed_bwd(void* stream, int32_t N, int32_t H, const int32_t* Z,
                        const float* g_h /*[N,H]*/, float* g_emb /*out [ZMAX+1,H]*/,
                        void* ws, size_t ws_bytes);
 
+/* hgnn_embed_bwd for callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc): same arguments without the workspace, same kernels, same result bit for bit. The
+ * scratch is an array of HGNN_EMBED_BWD_STATIC_MAX_BYTES built into the library's device code (every GPU the library
+ * runs on holds it until the process ends); the call allocates and frees nothing. WORKSPACE_TOO_SMALL when
+ * hgnn_embed_bwd_workspace_bytes(N, H) exceeds that size (ceil(N / 2048) * 95 * H * 4 bytes: e.g. N <= 176,128 at
+ * H = 256); use hgnn_embed_bwd then. All calls on one GPU share that array: calls that overlap on one GPU (two
+ * streams, two threads) race; calls on one stream are ordered and safe. Only enqueues work. */
+enum { HGNN_EMBED_BWD_STATIC_MAX_BYTES = 8 << 20 };
+int32_t hgnn_embed_bwd_static(void* stream, int32_t N, int32_t H, const int32_t* Z,
+                              const float* g_h /*[N,H]*/, float* g_emb /*out [ZMAX+1,H]*/);
+
 /* ---------------------------------------------------------------------------------------------
  * One message-passing layer of the shared stack (EGNN layer, positions held fixed):
  *   edge  e=(i<-j): m_e = silu(W2^T silu(W1^T [h_i ; h_j ; d2_e] + b1) + b2),  x_e = wx . m_e

@@ -19,7 +19,7 @@ ZMAX = 94
 EXPORTS = [
     "hgnn_last_error_string", "hgnn_version",
     "hgnn_radius_graph_workspace_bytes", "hgnn_radius_graph_count", "hgnn_radius_graph_fill",
-    "hgnn_embed_fwd", "hgnn_embed_bwd", "hgnn_embed_bwd_workspace_bytes",
+    "hgnn_embed_fwd", "hgnn_embed_bwd", "hgnn_embed_bwd_workspace_bytes", "hgnn_embed_bwd_static",
     "hgnn_set_side_stream", "hgnn_mp_layer_workspace_bytes", "hgnn_mp_layer_fwd", "hgnn_mp_layer_bwd",
     "hgnn_edge_rbf", "hgnn_edge_rbf_bwd", "hgnn_edge_geometry_fwd", "hgnn_edge_geometry_bwd",
     "hgnn_mp_layer_attr_workspace_bytes", "hgnn_mp_layer_attr_fwd", "hgnn_mp_layer_attr_bwd",
@@ -68,6 +68,7 @@ _rg_fill = _sig("hgnn_radius_graph_fill", vp, i32, i32, vp, vp, vp, vp, f32, vp,
                 vp, vp, vp, vp, vp, vp, vp, vp)
 _embed_fwd = _sig("hgnn_embed_fwd", vp, i32, i32, vp, vp, vp)
 _embed_bwd = _sig("hgnn_embed_bwd", vp, i32, i32, vp, vp, vp, vp, sz)
+_embed_bwd_static = _sig("hgnn_embed_bwd_static", vp, i32, i32, vp, vp, vp)
 _embed_bwd_ws = _sig("hgnn_embed_bwd_workspace_bytes", i32, i32, C.POINTER(sz))
 _mp_ws = _sig("hgnn_mp_layer_workspace_bytes", i32, i64, i32, i32, C.POINTER(sz), C.POINTER(sz))
 _mp_fwd = _sig("hgnn_mp_layer_fwd", vp, i32, i64, i32, i32, f32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
@@ -168,6 +169,13 @@ def embed_bwd_workspace_bytes(N, H):
 
 def embed_bwd(N, H, Z, g_h, g_emb, ws):
     _check(_embed_bwd(_stream(), N, H, _p(Z), _p(g_h), _p(g_emb), _p(ws), _nbytes(ws)))
+
+
+EMBED_BWD_STATIC_MAX_BYTES = 8 << 20
+
+
+def embed_bwd_static(N, H, Z, g_h, g_emb):
+    _check(_embed_bwd_static(_stream(), N, H, _p(Z), _p(g_h), _p(g_emb)))
 
 
 def mp_layer_workspace_bytes(N, E, H, dtype):

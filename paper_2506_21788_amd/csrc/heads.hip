@@ -456,6 +456,22 @@ extern "C" int32_t hgnn_embed_bwd_workspace_bytes(int32_t N, int32_t H, size_t* 
   return HGNN_OK;
 }
 
+// both entry points of the embedding gradient: `part` holds the per-chunk sums, every entry of which is written before
+// it is read, so it needs no clearing
+static int32_t embed_bwd_launch(hipStream_t st, int32_t N, int32_t H, const int32_t* Z, const float* g_h, float* g_emb,
+                                float* part) {
+  const int nchunk = (N + EMB_CHUNK - 1) / EMB_CHUNK;
+  ProfScope ps(PT_EMBED, st);
+  if (nchunk > 0) {
+    if (valid_H(H)) k_embed_bwd_part<<<dim3(HGNN_ZMAX + 1, nchunk), 256, 0, st>>>(N, H, Z, g_h, part);
+    else k_embed_bwd_part_any<<<dim3(HGNN_ZMAX + 1, nchunk), 256, 0, st>>>(N, H, Z, g_h, part);
+    HGNN_LAUNCH_CHECK("k_embed_bwd_part");
+  }
+  k_embed_bwd_sum<<<((HGNN_ZMAX + 1) * H + 255) / 256, 256, 0, st>>>(nchunk, H, part, g_emb);
+  HGNN_LAUNCH_CHECK("k_embed_bwd_sum");
+  return HGNN_OK;
+}
+
 extern "C" int32_t hgnn_embed_bwd(void* stream, int32_t N, int32_t H, const int32_t* Z, const float* g_h, float* g_emb,
                                   void* ws, size_t ws_bytes) {
   hipStream_t st = static_cast<hipStream_t>(stream);
@@ -464,16 +480,46 @@ extern "C" int32_t hgnn_embed_bwd(void* stream, int32_t N, int32_t H, const int3
   size_t need = 0;
   HGNN_TRY(hgnn_embed_bwd_workspace_bytes(N, H, &need));
   HGNN_REQUIRE(ws_bytes >= need, HGNN_ERR_WORKSPACE_TOO_SMALL, "embed_bwd workspace: need %zu bytes, got %zu", need, ws_bytes);
-  const int nchunk = (N + EMB_CHUNK - 1) / EMB_CHUNK;
-  ProfScope ps(PT_EMBED, st);
-  if (nchunk > 0) {
-    if (valid_H(H)) k_embed_bwd_part<<<dim3(HGNN_ZMAX + 1, nchunk), 256, 0, st>>>(N, H, Z, g_h, static_cast<float*>(ws));
-    else k_embed_bwd_part_any<<<dim3(HGNN_ZMAX + 1, nchunk), 256, 0, st>>>(N, H, Z, g_h, static_cast<float*>(ws));
-    HGNN_LAUNCH_CHECK("k_embed_bwd_part");
+  return embed_bwd_launch(st, N, H, Z, g_h, g_emb, static_cast<float*>(ws));
+}
+
+// ---------------------------------------------------------------------------------------------
+// The embedding gradient for callers that cannot allocate: the per-chunk sums live in a file-scope device array.
+// In host code the array's name only stands for the symbol; the memory is reached through the address that
+// hipGetSymbolAddress returns, asked for once per device (every device holds its own copy at its own address).
+// ---------------------------------------------------------------------------------------------
+constexpr size_t EMB_STATIC_BYTES = (size_t)HGNN_EMBED_BWD_STATIC_MAX_BYTES;
+static __device__ __align__(256) unsigned char scratch[EMB_STATIC_BYTES];
+
+static int32_t embed_static_scratch(float** out) {
+  constexpr int MAX_DEV = 64;
+  static void* ptr[MAX_DEV] = {};
+  int dev = -1;
+  HGNN_HIP(hipGetDevice(&dev));
+  HGNN_REQUIRE(dev >= 0 && dev < MAX_DEV, HGNN_ERR_HIP, "embed_bwd_static: device index %d out of range", dev);
+  if (!ptr[dev]) {
+    void* p = nullptr;
+    HGNN_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    HGNN_REQUIRE(p != nullptr, HGNN_ERR_HIP, "embed_bwd_static: no address for the scratch array");
+    ptr[dev] = p;
   }
-  k_embed_bwd_sum<<<((HGNN_ZMAX + 1) * H + 255) / 256, 256, 0, st>>>(nchunk, H, static_cast<const float*>(ws), g_emb);
-  HGNN_LAUNCH_CHECK("k_embed_bwd_sum");
+  *out = static_cast<float*>(ptr[dev]);
   return HGNN_OK;
+}
+
+extern "C" int32_t hgnn_embed_bwd_static(void* stream, int32_t N, int32_t H, const int32_t* Z, const float* g_h,
+                                         float* g_emb) {
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  HGNN_REQUIRE(N >= 0 && any_H(H), HGNN_ERR_BAD_SHAPE, "embed_bwd_static: bad N or H");
+  HGNN_REQUIRE(g_emb && (N == 0 || (Z && g_h)), HGNN_ERR_NULLPTR, "embed_bwd_static: null pointer");
+  size_t need = 0;
+  HGNN_TRY(hgnn_embed_bwd_workspace_bytes(N, H, &need));
+  HGNN_REQUIRE(need <= EMB_STATIC_BYTES, HGNN_ERR_WORKSPACE_TOO_SMALL,
+               "embed_bwd_static: N = %d, H = %d needs %zu bytes of scratch, the built-in array holds %zu "
+               "(use hgnn_embed_bwd with a workspace)", N, H, need, EMB_STATIC_BYTES);
+  float* part = nullptr;
+  HGNN_TRY(embed_static_scratch(&part));
+  return embed_bwd_launch(st, N, H, Z, g_h, g_emb, part);
 }
 
 extern "C" int32_t hgnn_pool_by_graph_fwd(void* stream, int32_t N, int32_t G, int32_t H, int32_t mode,
