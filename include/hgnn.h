@@ -75,8 +75,10 @@ int32_t hgnn_version(void);
  *
  * _count SYNCHRONISES the stream (it has to hand E to the host) and reports input errors:
  * graph_off not starting at 0 / not non-decreasing / not ending at N -> BAD_OFFSETS; a periodic graph
- * with |det cell| < 1e-6 A^3, or one that would need more than 127 images in a direction -> BAD_CELL;
- * E >= 2^31 -> OVERFLOW; rc <= 0 -> BAD_SHAPE.
+ * with |det cell| < 1e-6 A^3, or one that would need more than 127 images in a direction, or an atom of a periodic
+ * graph outside its cell (a fractional coordinate outside [-1e-5, 1 + 1e-5]) -> BAD_CELL;
+ * E >= 2^31 -> OVERFLOW; rc <= 0 -> BAD_SHAPE. All of them are found on the device and reported after that one
+ * synchronisation; the outputs are undefined then. _fill only enqueues work and may be called again after one _count.
  * ------------------------------------------------------------------------------------------- */
 int32_t hgnn_radius_graph_workspace_bytes(int32_t N, int32_t G, size_t* bytes_host);
 

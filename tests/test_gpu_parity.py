@@ -148,8 +148,48 @@ def test_radius_graph_error_paths():
     with pytest.raises(B.HgnnError) as e:
         B.radius_graph_count(N, G, None, _dev(b.graph_off, torch.int32), cell, pbc, 4.0, ws, row_ptr)
     assert e.value.code == -1
+    # an atom of a periodic graph outside its cell (moved by one lattice vector): reported, not silently short of edges
+    out = b.pos.copy()
+    out[int(b.graph_off[gi])] += b.cell[gi][0]
+    with pytest.raises(B.HgnnError) as e:
+        B.radius_graph_count(N, G, _dev(out, torch.float32), _dev(b.graph_off, torch.int32), cell, pbc, 4.0, ws, row_ptr)
+    assert e.value.code == -4 and "outside its cell" in str(e.value)
+    # ... while a non-periodic graph may sit anywhere
+    far = b.pos.copy()
+    mol = int(np.nonzero(b.pbc == 0)[0][0])
+    far[b.graph_off[mol]:b.graph_off[mol + 1]] += np.float32(1000.0)
+    assert B.radius_graph_count(N, G, _dev(far, torch.float32), _dev(b.graph_off, torch.int32), cell, pbc, 4.0, ws, row_ptr) > 0
     # the good call still works afterwards
     assert B.radius_graph_count(N, G, pos, _dev(b.graph_off, torch.int32), cell, pbc, 4.0, ws, row_ptr) > 0
+
+
+def test_radius_graph_fill_twice_after_one_count():
+    """The filling call keeps no state of its own: a second fill after one count gives the same graph."""
+    say("radius graph fill twice")
+    import torch
+    b = small_mixed_batch(4, n_mol=3, n_cry=3)
+    want = oracle.radius_graph(b.pos, b.graph_off, b.cell, b.pbc, 4.5)
+    g = gpu_graph(b, 4.5)
+    assert_graph_equal(g.to_numpy(), want)
+    from paper_2506_21788_amd import binding as B
+    for t in (g.dst, g.col, g.permT, g.colT_ptr):
+        t.fill_(-1)
+    B.radius_graph_fill(g.N, g.G, g.pos, g.graph_off, g.cell, g.pbc, g.rc, g.ws, g.tmp, g.row_ptr, g.E, g.dst, g.col,
+                        g.shift, g.d2, g.rvec, g.edge_graph_ptr, g.colT_ptr, g.permT)
+    torch.cuda.synchronize()
+    assert_graph_equal(g.to_numpy(), want)
+
+
+def test_radius_graph_crowded_single_bin():
+    """A dense cell thinner than two cutoffs: one bin whose 27 images hold several thousand candidates, which are
+    streamed through the staging buffer in chunks."""
+    say("radius graph crowded bin")
+    rng = np.random.default_rng(8)
+    graphs = [make_crystal(rng, 150, 7.0, 9.0, 0.7, 1, 50, max_density=0.4) for _ in range(2)]
+    b = concat_graphs(graphs)
+    want = oracle.radius_graph(b.pos, b.graph_off, b.cell, b.pbc, 5.0)
+    got = gpu_graph(b, 5.0).to_numpy()
+    assert_graph_equal(got, want)
 
 
 # ------------------------------------------------------------------------------------------------
