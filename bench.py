@@ -99,75 +99,70 @@ def calib_copy():
     print(json.dumps({"calib_copy_bytes_read": n * 4, "calib_copy_bytes_written": n * 4, "copies": 5}))
 
 
+def cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
 def cpu_baseline(P, target_edges=150000):
-    """The oracle, as it stands, on a bounded sample (the first graphs of the same batch)."""
+    """The oracle, as it stands (numpy float64), on a bounded sample of the same batch: the first graphs with about
+    target_edges edges with every host thread numpy's BLAS takes, and an eighth of that sample on one thread."""
     import numpy as np
     sys.path.insert(0, os.path.join(ROOT, "tests"))   # only this leg uses the oracle (through the tests' helpers)
     from hgnn_inputs import sub_batch
     from parity_util import oracle_graph, oracle_step
     b = P["batch"]
-    # grow the sample until the oracle graph has about target_edges edges (degree estimate ~30)
-    k, atoms = 0, 0
-    while k < b.G and atoms < target_edges / 30.0:
-        atoms += int(b.graph_off[k + 1] - b.graph_off[k])
-        k += 1
-    graphs = np.arange(k)
-    sb = sub_batch(b, graphs)
-    Ps = dict(P, batch=sb, gE=P["gE"][:k], gF=P["gF"][:sb.N])
-    t0 = time.perf_counter()
-    og = oracle_graph(Ps)
-    alpha = 1.0 / max(1.0, og["E"] / sb.N)
-    oracle_step(Ps, og, alpha)
-    dt = time.perf_counter() - t0
+
+    def run(target):
+        # grow the sample until the oracle graph has about `target` edges (degree estimate ~30)
+        k, atoms = 0, 0
+        while k < b.G and atoms < target / 30.0:
+            atoms += int(b.graph_off[k + 1] - b.graph_off[k])
+            k += 1
+        sb = sub_batch(b, np.arange(k))
+        Ps = dict(P, batch=sb, gE=P["gE"][:k], gF=P["gF"][:sb.N])
+        t0 = time.perf_counter()
+        og = oracle_graph(Ps)
+        alpha = 1.0 / max(1.0, og["E"] / sb.N)
+        oracle_step(Ps, og, alpha)
+        dt = time.perf_counter() - t0
+        return og["E"] / dt, f"first {k} graphs ({sb.N} atoms, {og['E']} edges), graph + fwd + bwd, {dt:.1f} s"
+
     try:
-        from threadpoolctl import threadpool_info
+        from threadpoolctl import threadpool_info, threadpool_limits
         cores = max([d.get("num_threads", 1) for d in threadpool_info()] + [1])
     except Exception:
-        cores = os.cpu_count() or 1
-    return {"value": og["E"] / dt, "unit": "edges/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"first {k} graphs of the batch ({sb.N} atoms, {og['E']} edges), numpy float64, "
-                      f"graph + fwd + bwd, {dt:.1f} s"}
+        threadpool_limits, cores = None, os.cpu_count() or 1
+    rate, what = run(target_edges)
+    out = {"value": rate, "unit": "edges/s", "cores": int(cores), "kind": "oracle", "cpu": cpu_model(),
+           "precision": "float64 (the oracle as the parity tests use it)", "sample": what}
+    if threadpool_limits is not None:
+        with threadpool_limits(limits=1):
+            r1, w1 = run(target_edges / 8)
+        out["single_thread"] = {"value": r1, "unit": "edges/s", "cores": 1, "sample": w1}
+    return out
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", default="cfg4")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--breakdown", action="store_true", help="print the per-kernel-class split to stderr")
-    ap.add_argument("--hip-graph", action="store_true",
-                    help="also time forward + backward replayed as one HIP graph (graph prebuilt)")
-    ap.add_argument("--rbf", type=int, default=0, metavar="K",
-                    help="K radial-basis edge attributes in place of d2 (2..16; every layer then runs on the fragment path)")
-    ap.add_argument("--pos-grad", action="store_true",
-                    help="the reverse pass also gives the gradient with respect to positions (fragment path, bf16)")
-    ap.add_argument("--move", action="store_true",
-                    help="the atoms move between layers (edge geometry recomputed per layer; implies --pos-grad)")
-    ap.add_argument("--calib-copy", action="store_true", help="only run a 1 GiB copy kernel (counter calibration)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU; no figure at several GPUs exists (--gpus 1 only)",
-              file=sys.stderr)
-        sys.exit(2)
-
-    if args.calib_copy:
-        calib_copy()
-        return
+def measure(name, steps, warmup, rbf=0, move=False, pos_grad=False, hip_graph=False, adamw=False):
+    """Time whole steps of one workload; returns (figures, problem). A step = radius graph + routing plan + forward +
+    backward on a batch that already sits in HBM."""
     import torch
     from hgnn_inputs import problem_from_config
     from paper_2506_21788_amd import binding as B
     from paper_2506_21788_amd.step import HotPath
 
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
-    P = problem_from_config(args.config, rbf_k=args.rbf or None, move=args.move, pos_grad=args.pos_grad)
+    P = problem_from_config(name, rbf_k=rbf or None, move=move, pos_grad=pos_grad)
     b, hp = P["batch"], P["hp"]
     hot = HotPath.from_problem(P)
     gE = torch.as_tensor(P["gE"]).cuda()
     gF = torch.as_tensor(P["gF"]).cuda()
 
-    for _ in range(max(1, args.warmup)):
+    for _ in range(max(1, warmup)):
         hot.step(gE, gF)
     torch.cuda.synchronize()
     E, N, G, H, L = hot.graph.E, b.N, b.G, hp["H"], hp["L"]
@@ -195,84 +190,155 @@ def main():
     B.profile_begin(1 << dom_id)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         hot.step(gE, gF)
     torch.cuda.synchronize()
-    t_full = (time.perf_counter() - t0) / args.steps
+    t_full = (time.perf_counter() - t0) / steps
     B.profile_end()
     dom_n, dom_ms = B.profile_read(dom_id)
 
-    # message passing only (graph prebuilt), for reference
+    # message passing only (graph and routing plan prebuilt), for reference
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         hot.step(gE, gF, with_graph=False)
     torch.cuda.synchronize()
-    t_mp = (time.perf_counter() - t0) / args.steps
+    t_mp = (time.perf_counter() - t0) / steps
 
-    # AdamW update of every weight buffer (not part of `value`: the metric is the message-passing step). The step's
-    # own weights are left alone: copies are updated, with the gradients of the last step.
-    params = [(w.clone(), g) for w, g in zip([*hot.W, hot.Whead, hot.emb], [*hot.gW, hot.gWhead, hot.g_emb])]
-    moments = [(torch.zeros_like(w), torch.zeros_like(w)) for w, _ in params]
-    n_params = sum(w.numel() for w, _ in params)
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    for t in range(1, 4):
-        for (w, g), (m, v) in zip(params, moments):
-            B.adamw_step(w, g, m, v, t)
-    ev0.record()
-    for t in range(4, 4 + args.steps):
-        for (w, g), (m, v) in zip(params, moments):
-            B.adamw_step(w, g, m, v, t)
-    ev1.record()
-    torch.cuda.synchronize()
-    adamw_ms = ev0.elapsed_time(ev1) / args.steps
+    avg_s = dom_ms / max(dom_n, 1) * 1e-3
+    roofline = roofline_of(dom, avg_s, N, E, H, hp["dtype"], read_traffic(name, dom))
+    roofline["launches_per_step"] = dom_n / steps
+    if roofline["traffic"] is not None:
+        roofline["traffic_source"] = (f"profiles/traffic_{name}.txt: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of this "
+                                      "kernel, measured in runs of their own (see profiles/), not in this run")
+
+    out = {
+        "ms_per_step": t_full * 1e3, "edges_per_s": E / t_full, "edge_layers_per_s": E * L / t_full,
+        "graphs_per_s": G / t_full, "dtype": hp["dtype"],
+        "config": {"workload": f"{name}: {hp['desc']}" + (f" + {rbf} radial-basis edge attributes" if rbf else "")
+                   + (" + moving atoms" if move else "") + (" + position gradients" if move or pos_grad else ""),
+                   "atoms": N, "graphs": G, "edges": E, "H": H,
+                   "layers": L, "sources": hp["S"], "cutoff": hp["rc"], "alpha": hot.alpha,
+                   "head_width": hp.get("Hh", H), "head_hidden_layers": hp.get("D", 1)},
+        "ms_per_step_graph_prebuilt": t_mp * 1e3, "edges_per_s_graph_prebuilt": E / t_mp,
+        "roofline": roofline,
+        "kernel_split_ms_per_step": {k: round(v["ms_per_step"], 4) for k, v in
+                                     sorted(split.items(), key=lambda kv: -kv[1]["ms_per_step"])},
+        "_split": split, "_shape": (N, E, H),
+    }
+
+    if adamw:
+        # AdamW update of every weight buffer (not part of `value`: the metric is the message-passing step). The
+        # step's own weights are left alone: copies are updated, with the gradients of the last step.
+        params = [(w.clone(), g) for w, g in zip([*hot.W, hot.Whead, hot.emb], [*hot.gW, hot.gWhead, hot.g_emb])]
+        moments = [(torch.zeros_like(w), torch.zeros_like(w)) for w, _ in params]
+        n_params = sum(w.numel() for w, _ in params)
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        for t in range(1, 4):
+            for (w, g), (m, v) in zip(params, moments):
+                B.adamw_step(w, g, m, v, t)
+        ev0.record()
+        for t in range(4, 4 + steps):
+            for (w, g), (m, v) in zip(params, moments):
+                B.adamw_step(w, g, m, v, t)
+        ev1.record()
+        torch.cuda.synchronize()
+        adamw_ms = ev0.elapsed_time(ev1) / steps
+        out["adamw"] = {"parameters": n_params, "buffers": len(params), "ms_per_update": adamw_ms,
+                        "GB_per_s": 28.0 * n_params / (adamw_ms * 1e-3) / 1e9,
+                        "note": "separate from value; 28 B per parameter (read w, g, m, v; write w, m, v)"}
 
     # the same forward + backward as one HIP graph (graph prebuilt), for launch-bound workloads
-    t_hg = None
-    if args.hip_graph:
+    if hip_graph:
         graph = hot.capture(gE, gF)
         for _ in range(3):
             graph.replay()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for _ in range(args.steps):
+        for _ in range(steps):
             graph.replay()
         torch.cuda.synchronize()
-        t_hg = (time.perf_counter() - t0) / args.steps
+        out["ms_per_step_graph_prebuilt_hip_graph"] = (time.perf_counter() - t0) / steps * 1e3
+    del hot
+    torch.cuda.empty_cache()
+    return out, P
 
-    avg_s = dom_ms / max(dom_n, 1) * 1e-3
-    roofline = roofline_of(dom, avg_s, N, E, H, hp["dtype"], read_traffic(args.config, dom))
-    roofline["launches_per_step"] = dom_n / args.steps
 
+def print_breakdown(name, m):
+    N, E, H = m["_shape"]
+    print(f"--- {name}: {m['ms_per_step']:.3f} ms/step", file=sys.stderr)
+    for k, v in sorted(m["_split"].items(), key=lambda kv: -kv[1]["ms_per_step"]):
+        per = v["ms_per_step"] / v["launches_per_step"] * 1e-3
+        r = roofline_of(k, per, N, E, H, m["dtype"])
+        print(f"{k:18s} {v['launches_per_step']:6.1f} launches  {v['ms_per_step']:9.3f} ms/step  "
+              f"{r['achieved']:10.1f} {r['unit']:8s} {100 * r['frac']:5.1f} % of {r['bound']} peak", file=sys.stderr)
+
+
+def public(m):
+    return {k: v for k, v in m.items() if not k.startswith("_")}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", default="cfg4", help="the workload `value` is quoted on")
+    ap.add_argument("--only", action="store_true", help="skip the short runs of the other configs")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--breakdown", action="store_true", help="print the per-kernel-class split to stderr")
+    ap.add_argument("--hip-graph", action="store_true",
+                    help="also time forward + backward replayed as one HIP graph (graph prebuilt)")
+    ap.add_argument("--rbf", type=int, default=0, metavar="K",
+                    help="K radial-basis edge attributes in place of d2 (2..16; every layer then runs on the fragment path)")
+    ap.add_argument("--pos-grad", action="store_true",
+                    help="the reverse pass also gives the gradient with respect to positions (fragment path, bf16)")
+    ap.add_argument("--move", action="store_true",
+                    help="the atoms move between layers (edge geometry recomputed per layer; implies --pos-grad)")
+    ap.add_argument("--calib-copy", action="store_true", help="only run a 1 GiB copy kernel (counter calibration)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; no figure at several GPUs exists (--gpus 1 only)",
+              file=sys.stderr)
+        sys.exit(2)
+
+    if args.calib_copy:
+        calib_copy()
+        return
+    import torch
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+
+    head, P = measure(args.config, args.steps, args.warmup, rbf=args.rbf, move=args.move, pos_grad=args.pos_grad,
+                      hip_graph=args.hip_graph, adamw=True)
+    if args.breakdown:
+        print_breakdown(args.config, head)
     out = {
         "metric": "message-passing edges/s (fwd+bwd), whole step incl. neighbour search, 1 MI355X",
-        "value": E / t_full, "unit": "edges/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": t_full * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": hp["dtype"], "data": "synthetic",
-        "config": {"workload": f"{args.config}: {hp['desc']}" + (f" + {args.rbf} radial-basis edge attributes" if args.rbf else "")
-                   + (" + moving atoms" if args.move else "") + (" + position gradients" if args.move or args.pos_grad else ""),
-                   "atoms": N, "graphs": G, "edges": E, "H": H,
-                   "layers": L, "sources": hp["S"], "cutoff": hp["rc"], "alpha": hot.alpha,
-                   "head_width": hp.get("Hh", H), "head_hidden_layers": hp.get("D", 1)},
-        "edge_layers_per_s": E * L / t_full, "graphs_per_s": G / t_full,
-        "ms_per_step_graph_prebuilt": t_mp * 1e3, "edges_per_s_graph_prebuilt": E / t_mp,
-        "ms_per_step_graph_prebuilt_hip_graph": None if t_hg is None else t_hg * 1e3,
-        "roofline": roofline,
-        "adamw": {"parameters": n_params, "buffers": len(params), "ms_per_update": adamw_ms,
-                  "GB_per_s": 28.0 * n_params / (adamw_ms * 1e-3) / 1e9,
-                  "note": "separate from value; 28 B per parameter (read w, g, m, v; write w, m, v)"},
+        "value": head["edges_per_s"], "unit": "edges/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": head["dtype"], "data": "synthetic", "config": head["config"],
+        "edge_layers_per_s": head["edge_layers_per_s"], "graphs_per_s": head["graphs_per_s"],
+        "ms_per_step_graph_prebuilt": head["ms_per_step_graph_prebuilt"],
+        "edges_per_s_graph_prebuilt": head["edges_per_s_graph_prebuilt"],
+        "ms_per_step_graph_prebuilt_hip_graph": head.get("ms_per_step_graph_prebuilt_hip_graph"),
+        "roofline": head["roofline"], "adamw": head["adamw"],
         "kernel_split_note": "per kernel class, timed alone (side stream off), over 2 untimed steps",
-        "kernel_split_ms_per_step": {k: round(v["ms_per_step"], 4) for k, v in
-                                     sorted(split.items(), key=lambda kv: -kv[1]["ms_per_step"])},
+        "kernel_split_ms_per_step": head["kernel_split_ms_per_step"],
     }
+    # the other workloads of the benchmark set, a few steps each: throughput and the roofline of their dominant kernel
+    if not args.only and not (args.rbf or args.move or args.pos_grad):
+        others = {}
+        for name in ("cfg1", "cfg2", "cfg3", "cfg4", "cfg5"):
+            if name == args.config:
+                others[name] = {k: v for k, v in public(head).items() if k != "adamw"}
+                continue
+            m, _ = measure(name, max(3, min(args.steps, 10)), 2)
+            if args.breakdown:
+                print_breakdown(name, m)
+            others[name] = public(m)
+        out["configs"] = others
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(P)
-    if args.breakdown:
-        for k, v in sorted(split.items(), key=lambda kv: -kv[1]["ms_per_step"]):
-            per = v["ms_per_step"] / v["launches_per_step"] * 1e-3
-            r = roofline_of(k, per, N, E, H, hp["dtype"])
-            print(f"{k:18s} {v['launches_per_step']:6.1f} launches  {v['ms_per_step']:9.3f} ms/step  "
-                  f"{r['achieved']:10.1f} {r['unit']:8s} {100 * r['frac']:5.1f} % of {r['bound']} peak", file=sys.stderr)
     print(json.dumps(out))
 
 

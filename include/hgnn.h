@@ -134,6 +134,10 @@ int32_t hgnn_embed_bwd_static(void* stream, int32_t N, int32_t H, const int32_t*
  *   W1[(2H+1),H] b1[H] W2[H,H] b2[H] wx[H] W3[2H,H] b3[H] W4[H,H] b4[H]     (6H^2 + 6H floats)
  * gW of _bwd has the same layout. `saved` (size from the workspace query) is written by _fwd and
  * read by _bwd of the same layer; `ws` is scratch. Rows with no edge get M_i = 0, v'_i = v_i.
+ * saved == NULL (both calls; H = 64, 128, 256 only): nothing is kept between the two calls and _bwd runs the forward
+ * pass of the layer once more to get what it needs (one more edge pass per layer in exchange for saved_bytes of
+ * memory per layer: 0.8 GB per layer on a 1.2 M-edge batch at H = 256). `ws` must then hold ws_bytes + saved_bytes
+ * + 512 + 24 N bytes of the query; the results are bit for bit those of the calls with a saved buffer.
  * _bwd takes g_h_out = dL/dh', g_v_out = dL/dv' and writes g_h_in = dL/dh, g_v_in = dL/dv and gW.
  * d2 and rvec are constants of the step (no gradient with respect to positions).
  * h_out may not alias h_in; g_h_in may not alias g_h_out.
@@ -142,7 +146,8 @@ int32_t hgnn_embed_bwd_static(void* stream, int32_t N, int32_t H, const int32_t*
  * float32 operands are UNIMPLEMENTED for them).
  * Errors: BAD_SHAPE for any other H or an unknown dtype; OVERFLOW if E > 2^31 - 129 or
  * N * 2H * 4 bytes reaches 4 GiB (the edge kernels index edges and gathered rows with 32 bits);
- * WORKSPACE_TOO_SMALL if ws / saved are smaller than the query says; UNIMPLEMENTED if saved == NULL.
+ * WORKSPACE_TOO_SMALL if ws / saved are smaller than the query says; UNIMPLEMENTED if saved == NULL at another
+ * width.
  * _bwd also enqueues weight-gradient work on a stream the library creates once (default priority). It
  * forks from and joins `stream` through events inside the call, so for the caller everything is
  * ordered on `stream`; the call that creates that stream must not run under stream capture.

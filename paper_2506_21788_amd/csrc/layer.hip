@@ -159,39 +159,19 @@ extern "C" int32_t hgnn_mp_layer_workspace_bytes(int32_t N, int64_t E, int32_t H
   return HGNN_OK;
 }
 
-// keep_xe: also keep x_e = wx . m_e per edge in the saved buffer (fused kernels only; the fragment path always does)
-static int32_t mp_layer_fwd_impl(void* stream, int32_t N, int64_t E, int32_t H, int32_t dtype, float alpha,
-                                 const int32_t* row_ptr, const int32_t* dst, const int32_t* col, const float* d2,
-                                 const float* rvec, const float* h_in, const float* v_in, const float* W, float* h_out,
-                                 float* v_out, void* saved, size_t saved_bytes, void* ws, size_t ws_bytes, bool keep_xe) {
-  hipStream_t st = static_cast<hipStream_t>(stream);
-  HGNN_TRY(check_layer_args(N, E, H, dtype));
-  if (N == 0) return HGNN_OK;
-  HGNN_REQUIRE(row_ptr && h_in && v_in && W && h_out && v_out && ws, HGNN_ERR_NULLPTR, "mp_layer_fwd: null pointer");
-  HGNN_REQUIRE(E == 0 || (dst && col && d2 && rvec), HGNN_ERR_NULLPTR, "mp_layer_fwd: null edge array");
-  HGNN_REQUIRE(saved != nullptr, HGNN_ERR_UNIMPLEMENTED,
-               "mp_layer_fwd without a saved buffer (recompute in backward) is not implemented");
-  HGNN_REQUIRE(h_out != h_in, HGNN_ERR_BAD_SHAPE, "h_out may not alias h_in");
-  if (wide_H(H)) {
-    size_t need_ws, need_saved;
-    wide_layer_sizes(N, E, H, 1, &need_ws, &need_saved);
-    HGNN_REQUIRE(ws_bytes >= need_ws, HGNN_ERR_WORKSPACE_TOO_SMALL, "mp_layer workspace: need %zu bytes, got %zu", need_ws, ws_bytes);
-    HGNN_REQUIRE(saved_bytes >= need_saved, HGNN_ERR_WORKSPACE_TOO_SMALL, "mp_layer saved buffer: need %zu bytes, got %zu", need_saved, saved_bytes);
-    WideLayerArgs a;
-    a.N = N; a.E = E; a.H = H; a.alpha = alpha;
-    a.row_ptr = row_ptr; a.dst = dst; a.col = col; a.d2 = d2; a.rvec = rvec;
-    a.h_in = h_in; a.v_in = v_in; a.W = W; a.h_out = h_out; a.v_out = v_out;
-    a.saved = saved; a.ws = ws;
-    return wide_layer_fwd(st, a);
-  }
-  const bool bf16 = dtype == HGNN_BF16;
-  LayerWs w = carve_ws(ws, N, E, H, bf16);
-  LayerSaved s = carve_saved(saved, N, E, H, bf16);
-  HGNN_REQUIRE(ws_bytes >= w.bytes, HGNN_ERR_WORKSPACE_TOO_SMALL, "mp_layer workspace: need %zu bytes, got %zu", w.bytes, ws_bytes);
-  HGNN_REQUIRE(saved_bytes >= s.bytes, HGNN_ERR_WORKSPACE_TOO_SMALL, "mp_layer saved buffer: need %zu bytes, got %zu", s.bytes, saved_bytes);
-  const LayerOff o(H);
+// Scratch behind the workspace proper for calls without a saved buffer: the saved tensors and two [N,3] vectors
+static size_t unsaved_extra_bytes(int N, int64_t E, int H, bool bf16) {
+  return carve_saved(nullptr, N, E, H, bf16).bytes + 2 * align_up((size_t)N * 3 * sizeof(float));
+}
 
-  // packed blocks: 0 W1a, 1 W1b, 2 W2, 3 W3a, 4 W3b, 5 W4
+// Everything of the forward pass that the reverse pass needs again (P|Q, z2 (a1), M, z3), written to `s`; also v_out.
+// Packs its own weight blocks into w.packed: 0 W1a, 1 W1b, 2 W2, 3 W3a, 4 W3b, 5 W4.
+// keep_xe: also keep x_e = wx . m_e per edge (fused kernels only; the fragment path always does)
+static int32_t layer_fwd_core(hipStream_t st, int32_t N, int64_t E, int32_t H, bool bf16, float alpha,
+                              const int32_t* row_ptr, const int32_t* dst, const int32_t* col, const float* d2,
+                              const float* rvec, const float* h_in, const float* v_in, const float* W, float* v_out,
+                              const LayerWs& w, const LayerSaved& s, bool keep_xe) {
+  const LayerOff o(H);
   PackArgs pk;
   pk.src = W;
   pk.dst = w.packed;
@@ -238,6 +218,48 @@ static int32_t mp_layer_fwd_impl(void* stream, int32_t N, int64_t E, int32_t H, 
     g.C = s.z3; g.ldc = H;
     HGNN_TRY(launch_gemm(st, H, bf16, g));
   }
+  return HGNN_OK;
+}
+
+static int32_t mp_layer_fwd_impl(void* stream, int32_t N, int64_t E, int32_t H, int32_t dtype, float alpha,
+                                 const int32_t* row_ptr, const int32_t* dst, const int32_t* col, const float* d2,
+                                 const float* rvec, const float* h_in, const float* v_in, const float* W, float* h_out,
+                                 float* v_out, void* saved, size_t saved_bytes, void* ws, size_t ws_bytes, bool keep_xe) {
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  HGNN_TRY(check_layer_args(N, E, H, dtype));
+  if (N == 0) return HGNN_OK;
+  HGNN_REQUIRE(row_ptr && h_in && v_in && W && h_out && v_out && ws, HGNN_ERR_NULLPTR, "mp_layer_fwd: null pointer");
+  HGNN_REQUIRE(E == 0 || (dst && col && d2 && rvec), HGNN_ERR_NULLPTR, "mp_layer_fwd: null edge array");
+  HGNN_REQUIRE(h_out != h_in, HGNN_ERR_BAD_SHAPE, "h_out may not alias h_in");
+  if (wide_H(H)) {
+    HGNN_REQUIRE(saved != nullptr, HGNN_ERR_UNIMPLEMENTED,
+                 "mp_layer_fwd without a saved buffer exists at H = 64, 128, 256 only (H = %d)", H);
+    size_t need_ws, need_saved;
+    wide_layer_sizes(N, E, H, 1, &need_ws, &need_saved);
+    HGNN_REQUIRE(ws_bytes >= need_ws, HGNN_ERR_WORKSPACE_TOO_SMALL, "mp_layer workspace: need %zu bytes, got %zu", need_ws, ws_bytes);
+    HGNN_REQUIRE(saved_bytes >= need_saved, HGNN_ERR_WORKSPACE_TOO_SMALL, "mp_layer saved buffer: need %zu bytes, got %zu", need_saved, saved_bytes);
+    WideLayerArgs a;
+    a.N = N; a.E = E; a.H = H; a.alpha = alpha;
+    a.row_ptr = row_ptr; a.dst = dst; a.col = col; a.d2 = d2; a.rvec = rvec;
+    a.h_in = h_in; a.v_in = v_in; a.W = W; a.h_out = h_out; a.v_out = v_out;
+    a.saved = saved; a.ws = ws;
+    return wide_layer_fwd(st, a);
+  }
+  const bool bf16 = dtype == HGNN_BF16;
+  LayerWs w = carve_ws(ws, N, E, H, bf16);
+  if (saved == nullptr) {
+    // nothing is kept for the reverse pass: the intermediates live behind the workspace proper for this call only
+    const size_t need = w.bytes + unsaved_extra_bytes(N, E, H, bf16);
+    HGNN_REQUIRE(ws_bytes >= need, HGNN_ERR_WORKSPACE_TOO_SMALL,
+                 "mp_layer workspace without a saved buffer: need %zu bytes (workspace + saved size), got %zu", need, ws_bytes);
+    saved = static_cast<char*>(ws) + w.bytes;
+    saved_bytes = ws_bytes - w.bytes;
+  }
+  LayerSaved s = carve_saved(saved, N, E, H, bf16);
+  HGNN_REQUIRE(ws_bytes >= w.bytes, HGNN_ERR_WORKSPACE_TOO_SMALL, "mp_layer workspace: need %zu bytes, got %zu", w.bytes, ws_bytes);
+  HGNN_REQUIRE(saved_bytes >= s.bytes, HGNN_ERR_WORKSPACE_TOO_SMALL, "mp_layer saved buffer: need %zu bytes, got %zu", s.bytes, saved_bytes);
+  const LayerOff o(H);
+  HGNN_TRY(layer_fwd_core(st, N, E, H, bf16, alpha, row_ptr, dst, col, d2, rvec, h_in, v_in, W, v_out, w, s, keep_xe));
   {  // h' = h + silu(z3) W4 + b4
     GemmArgs g;
     g.A[0] = s.z3; g.lda[0] = H; g.a_silu = 1;
@@ -271,12 +293,14 @@ static int32_t mp_layer_bwd_impl(void* stream, int32_t N, int64_t E, int32_t H, 
   hipStream_t st = static_cast<hipStream_t>(stream);
   HGNN_TRY(check_layer_args(N, E, H, dtype));
   HGNN_REQUIRE(gW && W && ws, HGNN_ERR_NULLPTR, "mp_layer_bwd: null pointer");
-  HGNN_REQUIRE(N == 0 || (row_ptr && colT_ptr && h_in && saved && g_h_out && g_v_out && g_h_in && g_v_in),
+  HGNN_REQUIRE(N == 0 || (row_ptr && colT_ptr && h_in && g_h_out && g_v_out && g_h_in && g_v_in),
                HGNN_ERR_NULLPTR, "mp_layer_bwd: null pointer");
   HGNN_REQUIRE(E == 0 || (dst && col && d2 && rvec && permT), HGNN_ERR_NULLPTR, "mp_layer_bwd: null edge array");
   HGNN_REQUIRE(N == 0 || g_h_in != g_h_out, HGNN_ERR_BAD_SHAPE, "g_h_in may not alias g_h_out");
   if (N == 0) return launch_fill_f32(st, gW, LayerOff(H).total, 0.f);
   if (wide_H(H)) {
+    HGNN_REQUIRE(saved != nullptr, HGNN_ERR_UNIMPLEMENTED,
+                 "mp_layer_bwd without a saved buffer exists at H = 64, 128, 256 only (H = %d)", H);
     size_t need_ws, need_saved;
     wide_layer_sizes(N, E, H, 1, &need_ws, &need_saved);
     HGNN_REQUIRE(ws_bytes >= need_ws, HGNN_ERR_WORKSPACE_TOO_SMALL, "mp_layer workspace: need %zu bytes, got %zu", need_ws, ws_bytes);
@@ -291,11 +315,27 @@ static int32_t mp_layer_bwd_impl(void* stream, int32_t N, int64_t E, int32_t H, 
   }
   const bool bf16 = dtype == HGNN_BF16;
   LayerWs w = carve_ws(ws, N, E, H, bf16);
+  const bool recompute = saved == nullptr;
+  if (recompute) {
+    HGNN_REQUIRE(g_d2 == nullptr && g_rvec == nullptr, HGNN_ERR_BAD_SHAPE,
+                 "edge gradients need the saved buffer of hgnn_mp_layer_attr_fwd");
+    const size_t need = w.bytes + unsaved_extra_bytes(N, E, H, bf16);
+    HGNN_REQUIRE(ws_bytes >= need, HGNN_ERR_WORKSPACE_TOO_SMALL,
+                 "mp_layer workspace without a saved buffer: need %zu bytes (workspace + saved size), got %zu", need, ws_bytes);
+    saved = static_cast<char*>(ws) + w.bytes;
+    saved_bytes = ws_bytes - w.bytes;
+  }
   LayerSaved s = carve_saved(const_cast<void*>(saved), N, E, H, bf16);
   HGNN_REQUIRE(ws_bytes >= w.bytes, HGNN_ERR_WORKSPACE_TOO_SMALL, "mp_layer workspace: need %zu bytes, got %zu", w.bytes, ws_bytes);
   HGNN_REQUIRE(saved_bytes >= s.bytes, HGNN_ERR_WORKSPACE_TOO_SMALL, "mp_layer saved buffer: need %zu bytes, got %zu", s.bytes, saved_bytes);
   const LayerOff o(H);
   const long HH = (long)H * H;
+  if (recompute) {
+    // the forward pass of this layer once more, up to z3 (its v' goes to scratch; the input v does not matter for
+    // anything the reverse pass reads, so any valid [N,3] array serves)
+    float* v_scratch = reinterpret_cast<float*>(static_cast<char*>(const_cast<void*>(saved)) + s.bytes);
+    HGNN_TRY(layer_fwd_core(st, N, E, H, bf16, alpha, row_ptr, dst, col, d2, rvec, h_in, g_v_out, W, v_scratch, w, s, false));
+  }
 
   // transposed blocks: 0 W4^T, 1 W3a^T, 2 W3b^T, 3 W2^T, 4 W1a^T, 5 W1b^T
   PackArgs pk;

@@ -95,7 +95,7 @@ class HotPath:
         self.graph = Graph(self.pos, self.graph_off, self.cell, self.pbc, rc)
         self._alloc_E = None
         self.plan = torch.empty(B.multihead_plan_ints(self.N, self.G, S), dtype=torch.int32, device="cuda")
-        B.multihead_plan(self.N, self.G, S, self.graph_off, self.source_id, self.plan)
+        self.build_plan()
 
     @classmethod
     def from_problem(cls, P, alpha=None, **kw):
@@ -104,6 +104,10 @@ class HotPath:
         return cls(b, hp["rc"], hp["H"], hp["L"], hp["S"], hp["dtype"], P["emb"], P["Ws"], P["Wh"], alpha=alpha,
                    Hh=hp.get("Hh"), D=hp.get("D"), rbf_k=hp.get("rbf_k"), move=hp.get("move", False),
                    pos_grad=hp.get("pos_grad", False), **kw)
+
+    def build_plan(self):
+        """Routing of graphs and atoms to their source's branch (depends on the batch only)."""
+        B.multihead_plan(self.N, self.G, self.S, self.graph_off, self.source_id, self.plan)
 
     # -- graph ---------------------------------------------------------------------------------
     def build_graph(self):
@@ -236,8 +240,11 @@ class HotPath:
         self.g_h0, self.g_v0 = self.g_h[at(0)], self.g_v[at(0)]
 
     def step(self, g_energy, g_force, with_graph=True):
+        """One whole step. with_graph: everything that depends on the batch is rebuilt as for a new batch (radius
+        graph and routing plan)."""
         if with_graph:
             self.build_graph()
+            self.build_plan()
         self.forward()
         self.backward(g_energy, g_force)
 

@@ -60,6 +60,47 @@ def _run_layer(N, E, H, dtype, seed):
         assert e <= (tol["fwd"] if k in ("h", "v") else tol["grad"]), (k, e)
 
 
+@pytest.mark.parametrize("H,dtype,N,E", [(256, "bf16", 700, 40001), (128, "f32", 300, 8191), (64, "bf16", 90, 1000),
+                                         (256, "f32", 50, 0)])
+def test_layer_without_saved_buffer_recomputes(H, dtype, N, E):
+    """saved == NULL in both calls: the reverse pass recomputes what the forward pass would have kept; every output
+    equals the saved-buffer calls bit for bit."""
+    import torch
+    from paper_2506_21788_amd import binding as B
+    rng = np.random.default_rng(H + E)
+    row_ptr, dst, col, d2, rvec = _edges(rng, N, E)
+    colT_ptr, permT = oracle.transpose_plan(col, N)
+    dt = {"f32": B.F32, "bf16": B.BF16}[dtype]
+    dev = lambda a: torch.as_tensor(a).cuda()
+    t = dict(row_ptr=dev(row_ptr), dst=dev(dst), col=dev(col), d2=dev(d2), rvec=dev(rvec), colT=dev(colT_ptr),
+             permT=dev(permT.astype(np.int32)), h=dev(rng.standard_normal((N, H)).astype(np.float32)),
+             v=dev((rng.standard_normal((N, 3)) * 0.3).astype(np.float32)), W=dev(init_layer_weights(rng, H).astype(np.float32)),
+             gh=dev(rng.standard_normal((N, H)).astype(np.float32)), gv=dev(rng.standard_normal((N, 3)).astype(np.float32)))
+    alpha = 1.0 / max(1.0, E / N)
+    ws_b, saved_b = B.mp_layer_workspace_bytes(N, E, H, dt)
+    outs = []
+    for keep in (True, False):
+        ws = torch.empty(ws_b + (0 if keep else saved_b + 512 + 24 * N), dtype=torch.uint8, device="cuda")
+        saved = torch.empty(saved_b, dtype=torch.uint8, device="cuda") if keep else None
+        h_out, v_out = torch.full_like(t["h"], float("nan")), torch.full_like(t["v"], float("nan"))
+        g_h, g_v, gW = torch.full_like(t["h"], float("nan")), torch.full_like(t["v"], float("nan")), torch.full_like(t["W"], float("nan"))
+        B.mp_layer_fwd(N, E, H, dt, alpha, t["row_ptr"], t["dst"], t["col"], t["d2"], t["rvec"], t["h"], t["v"], t["W"],
+                       h_out, v_out, saved, ws)
+        ws.fill_(0x5a)             # nothing of the forward call survives in the workspace
+        B.mp_layer_bwd(N, E, H, dt, alpha, t["row_ptr"], t["dst"], t["col"], t["d2"], t["rvec"], t["colT"], t["permT"],
+                       t["h"], t["W"], saved, t["gh"], t["gv"], g_h, g_v, gW, ws)
+        torch.cuda.synchronize()
+        outs.append([x.cpu().numpy() for x in (h_out, v_out, g_h, g_v, gW)])
+    for a, b in zip(*outs):
+        assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+    # a workspace of the plain size is refused
+    ws = torch.empty(ws_b, dtype=torch.uint8, device="cuda")
+    with pytest.raises(B.HgnnError) as e:
+        B.mp_layer_fwd(N, E, H, dt, alpha, t["row_ptr"], t["dst"], t["col"], t["d2"], t["rvec"], t["h"], t["v"], t["W"],
+                       torch.empty_like(t["h"]), torch.empty_like(t["v"]), None, ws)
+    assert e.value.code == -6
+
+
 # With bf16 operands at H = 256 the W2 gradient has a branch-free launch over an even number of whole 32-edge blocks
 # per workgroup (needs at least 2 x 256 blocks = 16384 edges) and a checking launch for the rest; the fused edge
 # kernels work on 64-edge tiles with a masked last tile.
