@@ -42,6 +42,15 @@ int32_t set_error(int32_t code, const char* fmt, ...);
 
 inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 
+// Wait for a stream by polling: the calls that hand a count or an error to the host sit in the middle of a step,
+// where the wake-up latency of a blocking wait would leave the GPU idle.
+inline hipError_t wait_stream(hipStream_t st) {
+  hipError_t e;
+  while ((e = hipStreamQuery(st)) == hipErrorNotReady) {
+  }
+  return e;
+}
+
 // Carves aligned sub-buffers out of a caller workspace; `used()` is what a size query reports.
 struct Carver {
   char* base;

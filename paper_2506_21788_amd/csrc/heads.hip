@@ -566,7 +566,7 @@ extern "C" int32_t hgnn_multihead_plan(void* stream, int32_t N, int32_t G, int32
   HGNN_LAUNCH_CHECK("k_plan_graphs");
   int32_t status = 0;
   HGNN_HIP(hipMemcpyAsync(&status, v.status, sizeof(status), hipMemcpyDeviceToHost, st));
-  HGNN_HIP(hipStreamSynchronize(st));
+  HGNN_HIP(wait_stream(st));
   HGNN_REQUIRE(status == 0, HGNN_ERR_BAD_SOURCE_ID, "a source id lies outside [0, %d)", S);
   if (N > 0) {
     k_plan_atoms<<<nb64(N, 256), 256, 0, st>>>(N, G, graph_off, v);

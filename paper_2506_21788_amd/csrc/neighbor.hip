@@ -116,9 +116,47 @@ size_t scan_scratch_ints(int64_t n) {
   return (size_t)(2 * (nb + 2));  // int64 entries counted in int32 units
 }
 
+// short inputs: one workgroup walks the array in chunks of SCAN_BLK with a running carry (one launch instead of three);
+// leaves the same block sums and grand total behind as the three-kernel form
+__global__ void k_scan_small(const int32_t* __restrict__ in, int32_t* __restrict__ out, int64_t n,
+                             long long* __restrict__ blocksum) {
+  __shared__ int sh[SCAN_T];
+  long long carry = 0;
+  const int64_t nb = (n + SCAN_BLK - 1) / SCAN_BLK;
+  for (int64_t b = 0; b < nb; ++b) {
+    const int64_t base = b * SCAN_BLK + (int64_t)threadIdx.x * SCAN_PER;
+    int v[SCAN_PER];
+    int s = 0;
+#pragma unroll
+    for (int k = 0; k < SCAN_PER; ++k) {
+      v[k] = (base + k < n) ? in[base + k] : 0;
+      s += v[k];
+    }
+    int tot;
+    int ex = block_exclusive_scan_256(s, &tot, sh);
+#pragma unroll
+    for (int k = 0; k < SCAN_PER; ++k) {
+      if (base + k < n) out[base + k] = (int32_t)(carry + ex);
+      ex += v[k];
+    }
+    if (threadIdx.x == 0) blocksum[b] = carry;
+    carry += tot;
+  }
+  if (threadIdx.x == 0) {
+    blocksum[nb] = carry;
+    out[n] = (int32_t)carry;
+  }
+}
+constexpr int64_t SCAN_SMALL_MAX = 16 * SCAN_BLK;
+
 int32_t exclusive_scan_i32(hipStream_t st, const int32_t* in, int32_t* out, int64_t n, int32_t* scratch) {
   long long* bs = reinterpret_cast<long long*>(scratch);
   int64_t nb = (n + SCAN_BLK - 1) / SCAN_BLK;
+  if (n <= SCAN_SMALL_MAX) {
+    k_scan_small<<<dim3(1), dim3(SCAN_T), 0, st>>>(in, out, n, bs);
+    HGNN_LAUNCH_CHECK("k_scan_small");
+    return HGNN_OK;
+  }
   if (nb > 0) {
     k_scan_local<<<dim3((unsigned)nb), dim3(SCAN_T), 0, st>>>(in, out, n, bs);
     HGNN_LAUNCH_CHECK("k_scan_local");
@@ -900,7 +938,7 @@ extern "C" int32_t hgnn_radius_graph_count(void* stream, int32_t N, int32_t G, c
     k_fill_i32<<<1, 64, 0, st>>>(row_ptr, 1, 0);
     k_fill_i32<<<1, 64, 0, st>>>(w.colT_ptr, 1, 0);
     HGNN_LAUNCH_CHECK("k_fill_i32");
-    HGNN_HIP(hipStreamSynchronize(st));
+    HGNN_HIP(wait_stream(st));
     return HGNN_OK;
   }
   // Everything below is enqueued in one go: a bad offset or cell is recorded in status[0], leaves every later
@@ -944,7 +982,7 @@ extern "C" int32_t hgnn_radius_graph_count(void* stream, int32_t N, int32_t G, c
   int64_t nbs = ((int64_t)N + SCAN_BLK - 1) / SCAN_BLK;
   HGNN_HIP(hipMemcpyAsync(&total, reinterpret_cast<long long*>(w.scan) + nbs, sizeof(total), hipMemcpyDeviceToHost, st));
   HGNN_HIP(hipMemcpyAsync(status_h, w.status, sizeof(status_h), hipMemcpyDeviceToHost, st));
-  HGNN_HIP(hipStreamSynchronize(st));
+  HGNN_HIP(wait_stream(st));
   HGNN_REQUIRE(!(status_h[0] & ST_BAD_OFFSETS), HGNN_ERR_BAD_OFFSETS,
                "graph_off must start at 0, be non-decreasing and end at N");
   HGNN_REQUIRE(!(status_h[0] & ST_BAD_CELL), HGNN_ERR_BAD_CELL,

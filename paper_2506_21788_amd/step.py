@@ -243,8 +243,10 @@ class HotPath:
         """One whole step. with_graph: everything that depends on the batch is rebuilt as for a new batch (radius
         graph and routing plan)."""
         if with_graph:
-            self.build_graph()
+            # the plan first: both calls wait for the stream once, and the second wait is short when nothing but the
+            # counting pass of the graph sits between them; the filling pass then runs ahead of the forward pass
             self.build_plan()
+            self.build_graph()
         self.forward()
         self.backward(g_energy, g_force)
 
