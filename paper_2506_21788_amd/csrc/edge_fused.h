@@ -37,6 +37,11 @@ struct EdgeFwdArgs {
   const float* b2;     // [H]
   void* a1_pk;         // out: silu(z1), operand-packed (bf16 or fp32); null: not stored
   void* z2_vm;         // out: z2, v-major (bf16 or fp32)
+  // k > 1 edge attributes in place of d2 (bf16 operands only): z1 = P[dst] + Q[col] + attr_e . W1a, the last term
+  // formed on the matrix cores from a bf16 copy of the tile's attributes; null: the d2 term above
+  const float* attr = nullptr;   // [E,k]
+  int k = 0;                     // 2..16
+  const float* W1a = nullptr;    // [k,H] rows of W1 that act on the attributes
 };
 int32_t launch_edge_fwd(hipStream_t st, int H, bool bf16, const EdgeFwdArgs& a);
 
@@ -64,8 +69,15 @@ struct EdgeBwdArgs {
   float* colpart;      // scratch: [splits][3][H] partial column sums (b2, wx, w1d)
   float* g_b2;         // out [H]
   float* g_wx;         // out [H]
-  float* g_w1d;        // out [H]
+  float* g_w1d;        // out [H] (null with edge attributes)
+  // k > 1 edge attributes in place of d2 (see EdgeFwdArgs); g_W1a[j][c] = sum_e attr[e][j] g_z1[e][c]
+  const float* attr = nullptr;
+  int k = 0;
+  const float* W1a = nullptr;
+  float* attrpart = nullptr;     // scratch: [splits][k][H] partial sums, edge_bwd_attrpart_floats()
+  float* g_W1a = nullptr;        // out [k,H]
 };
+size_t edge_bwd_attrpart_floats(int H);
 size_t edge_bwd_colpart_floats(int H);
 int32_t launch_edge_bwd(hipStream_t st, int H, bool bf16, const EdgeBwdArgs& a);
 
@@ -90,5 +102,9 @@ int32_t launch_wgrad_frag_recompute(hipStream_t st, int H, int64_t E, const int3
 int32_t launch_segsum_vm(hipStream_t st, int H, bool bf16, int N, const int32_t* ptr, const int32_t* perm,
                          const void* X_vm, float* out, int ldo, int tag, const float* wdot = nullptr,
                          float* dot = nullptr);
+
+// g_attr[e][j] = sum_c X[e][c] W1a[j][c] for every edge (X = g_z1, v-major bf16; 2 <= k <= 16): the gradient with
+// respect to k > 1 edge attributes, for callers that ask for it
+int32_t launch_gattr_vm(hipStream_t st, int H, int64_t E, const void* X_vm, const float* W1a, int k, float* g_attr);
 
 }  // namespace hgnn

@@ -243,7 +243,7 @@ __device__ __forceinline__ int fetch_edge_scalar(const int32_t* __restrict__ dst
   switch (which) {
     case 0: return dst[e];
     case 1: return col[e];
-    case 2: return __float_as_int(d2[e]);
+    case 2: return d2 ? __float_as_int(d2[e]) : 0;
     default: return __float_as_int(cvec[e]);
   }
 }
@@ -324,6 +324,82 @@ __device__ __forceinline__ unsigned rows8_mask(int eb, int vh, int g, int E) {
 }
 
 // ---------------------------------------------------------------------------------------------
+// k > 1 edge attributes (bf16 operands): the term attr_e . W1a of z1 is one matrix-core step per 32 x 32 block
+// ([32 edges x 16 attribute slots] x [16 x 32 columns]) out of a bf16 copy of the tile's attributes in LDS, in the
+// accumulator mapping in which z1 is formed anyway. Attribute slots beyond k hold zeros.
+// ---------------------------------------------------------------------------------------------
+constexpr int ATTR_K = 16;                        // attribute slots per edge in LDS
+constexpr int ATTR_TILE = 64 * ATTR_K;            // bf16 elements of one tile's attributes, [64 edges][16]
+constexpr int ATTR_T_PITCH = 72;                  // row pitch of the transposed copy [16][64 edges] (reverse kernel)
+constexpr int ATTR_T_TILE = ATTR_K * ATTR_T_PITCH;
+
+// thread tid's share of a tile's attributes: edge tid/4, slots 4*(tid%4) .. +3, as two bf16 pairs (zeros beyond E / k)
+__device__ __forceinline__ uint2 fetch_attr4(const float* __restrict__ attr, int k, int tile, int tile_end, int E, int tid) {
+  const int row = tid >> 2, q = tid & 3;
+  const int e = tile * 64 + row;
+  float a[4] = {0.f, 0.f, 0.f, 0.f};
+  if (tile < tile_end && e < E) {
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+      if (4 * q + t < k) a[t] = attr[(size_t)e * k + 4 * q + t];
+  }
+  return make_uint2(pack_bf16x2(a[0], a[1]), pack_bf16x2(a[2], a[3]));
+}
+__device__ __forceinline__ void store_attr4(unsigned short* at, int tid, uint2 v) {
+  *reinterpret_cast<uint2*>(at + (tid >> 2) * ATTR_K + 4 * (tid & 3)) = v;
+}
+// the same four values into the transposed copy: slot-major, edges contiguous
+__device__ __forceinline__ void store_attr4_t(unsigned short* att, int tid, uint2 v) {
+  const int row = tid >> 2, q = tid & 3;
+  att[(4 * q + 0) * ATTR_T_PITCH + row] = (unsigned short)(v.x & 0xffffu);
+  att[(4 * q + 1) * ATTR_T_PITCH + row] = (unsigned short)(v.x >> 16);
+  att[(4 * q + 2) * ATTR_T_PITCH + row] = (unsigned short)(v.y & 0xffffu);
+  att[(4 * q + 3) * ATTR_T_PITCH + row] = (unsigned short)(v.y >> 16);
+}
+// B operand of the attribute step for this lane's column n: rows 8*(lane>>5) .. +7 of W1a (zeros beyond k)
+__device__ __forceinline__ bf16x8_t attr_weight_operand(const float* __restrict__ W1a, int k, int H, int n, int lane) {
+  typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
+  u32x4_t w;
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    const int r = (lane >> 5) * 8 + 2 * t;
+    const float v0 = r < k ? W1a[(size_t)r * H + n] : 0.f;
+    const float v1 = r + 1 < k ? W1a[(size_t)(r + 1) * H + n] : 0.f;
+    w[t] = pack_bf16x2(v0, v1);
+  }
+  return __builtin_bit_cast(bf16x8_t, w);
+}
+// A operand of the attribute gradient g_W1a += attr^T g_z1 for the 16 edges (block rblk, register half vh) whose
+// g_z1 a lane holds in 8 registers: lane (slot m = lane & 31, half g) takes attr[e][m] of edges 16vh + 4g + 0..3 and
+// 16vh + 8 + 4g + 0..3 of the block from the transposed copy (slots >= 16 do not exist: zeros)
+__device__ __forceinline__ bf16x8_t attr_t_operand(const unsigned short* att, int rblk, int vh, int lane) {
+  typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
+  const int m = lane & 31, g = lane >> 5;
+  u32x4_t w = {0u, 0u, 0u, 0u};
+  if (m < ATTR_K) {
+    const unsigned short* r = att + m * ATTR_T_PITCH + rblk * 32 + 16 * vh + 4 * g;
+    const uint2 lo = *reinterpret_cast<const uint2*>(r);
+    const uint2 hi = *reinterpret_cast<const uint2*>(r + 8);
+    w[0] = lo.x; w[1] = lo.y; w[2] = hi.x; w[3] = hi.y;
+  }
+  return __builtin_bit_cast(bf16x8_t, w);
+}
+__device__ __forceinline__ bf16x8_t pack_operand8(const float* v) {
+  typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
+  const u32x4_t w = {pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7])};
+  return __builtin_bit_cast(bf16x8_t, w);
+}
+// attribute term of z1 for the 32-edge block rblk of the tile: one accumulator block per column block of this lane
+template <int CB>
+__device__ __forceinline__ void attr_z1_block(const unsigned short* at, int rblk, int lane, const bf16x8_t (&bW)[CB],
+                                              f32x16_t (&zat)[CB]) {
+  const f32x16_t zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  const bf16x8_t a = *reinterpret_cast<const bf16x8_t*>(at + (rblk * 32 + (lane & 31)) * ATTR_K + (lane >> 5) * 8);
+#pragma unroll
+  for (int j = 0; j < CB; ++j) zat[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bW[j], zero, 0, 0, 0);
+}
+
+// ---------------------------------------------------------------------------------------------
 // forward
 // ---------------------------------------------------------------------------------------------
 // Gathers of one group of 8 edges (bf16 pairs): the pair words of P[dst] and Q[col] and d2, from the tile's
@@ -348,17 +424,26 @@ __device__ __forceinline__ void fwd_issue_group(const void* PQ, const int* s, in
 // One tile of the forward kernel. FULL: all TM edges of the tile exist (no masking anywhere).
 // wp0 / wq0 / dd0 (bf16 pairs only): the gathers of this tile's first group, asked for at the end of the previous
 // tile; on return they hold those of the next tile's first group.
-template <int H, bool BF16, bool BRES, bool FULL>
+// ATTR: k > 1 edge attributes take the place of the d2 term (at: this tile's attributes in LDS, at_next / nxa: where and
+// what to store for the next tile, bW1a: this lane's attribute weights as matrix-core operands).
+template <int H, bool BF16, bool BRES, bool FULL, bool ATTR>
 __device__ __forceinline__ void edge_fwd_tile(
     const EdgeFwdArgs& p, unsigned char* smem, const int* s, int* s_next, int nxt, int tile, int E, int tid, int wr,
     int wc, int lane, const float (&w1d)[ECfg<H, BF16>::CB], const float (&b2)[ECfg<H, BF16>::CB],
     const typename BFrag<H, BF16>::type (&breg)[BRES ? BFrag<H, BF16>::NKB : 1][ECfg<H, BF16>::CB],
-    unsigned (&wp0)[8], unsigned (&wq0)[8], float (&dd0)[8]) {
+    unsigned (&wp0)[8], unsigned (&wq0)[8], float (&dd0)[8], const unsigned short* at, unsigned short* at_next,
+    uint2 nxa, const bf16x8_t (&bW1a)[ECfg<H, BF16>::CB]) {
   using C = ECfg<H, BF16>;
   constexpr bool PAIRS = BF16 && C::CB == 2;
   const int g = lane >> 5, x = lane & 31;
   // byte offset of this lane's first column inside a row: word wc*32 + x of bf16 pairs, else column wc*CB*32 + x
   const unsigned colb = (unsigned)((PAIRS ? wc * 32 : wc * C::CB * 32) + x) * 4u;
+  // attribute term of z1 for all of this wavefront's blocks (the accumulator registers are free in this phase)
+  f32x16_t zat[ATTR ? C::RB : 1][C::CB];
+  if constexpr (ATTR) {
+#pragma unroll
+    for (int i = 0; i < C::RB; ++i) attr_z1_block<C::CB>(at, wr * C::RB + i, lane, bW1a, zat[i]);
+  }
   // ---- produce a1 for this wavefront's blocks: memory (operand-packed) and LDS (row-major)
   if constexpr (PAIRS && FULL) {
     // Groups of 8 edges, software-pipelined: the gathers of the next group are in flight while this one is turned
@@ -388,7 +473,8 @@ __device__ __forceinline__ void edge_fwd_tile(
         for (int u = 0; u < 8; ++u) {
           const float zp = j == 0 ? __uint_as_float(wpc[u] << 16) : __uint_as_float(wpc[u] & 0xffff0000u);
           const float zq = j == 0 ? __uint_as_float(wqc[u] << 16) : __uint_as_float(wqc[u] & 0xffff0000u);
-          vals[u] = silu_f(zp + zq + ddc[u] * w1d[j]);
+          if constexpr (ATTR) vals[u] = silu_f(zp + zq + zat[gi >> 1][j][8 * (gi & 1) + u]);
+          else vals[u] = silu_f(zp + zq + ddc[u] * w1d[j]);
         }
         emit_half<BF16, C::STRIDE>(smem, rblk * 32, g, cblk * 32 + x, vals, vh, p.a1_pk, (size_t)eb * C::NCB + cblk, lane);
       }
@@ -416,7 +502,8 @@ __device__ __forceinline__ void edge_fwd_tile(
         float vals[8];
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
-          vals[u] = silu_f(z[j][u]);
+          if constexpr (ATTR) vals[u] = silu_f(z[j][u] + zat[i][j][8 * vh + u]);
+          else vals[u] = silu_f(z[j][u]);
           if (!FULL && !((ok >> u) & 1u)) vals[u] = 0.f;
         }
         emit_half<BF16, C::STRIDE>(smem, rblk * 32, g, n, vals, vh, p.a1_pk, (size_t)eb * C::NCB + cblk, lane);
@@ -434,6 +521,7 @@ __device__ __forceinline__ void edge_fwd_tile(
   if constexpr (BRES) tile_mma_res<H, BF16>(smem, wr, lane, breg, acc);
   else tile_mma<H, BF16>(smem, p.W2p, wr, wc, lane, acc);
   if (tid < 3 * C::TM) s_next[tid] = nxt;
+  if constexpr (ATTR) store_attr4(at_next, tid, nxa);
   __syncthreads();
   // ---- z2 = acc + b2, stored v-major (as bf16 pairs of this lane's two column blocks when PAIRS)
 #pragma unroll
@@ -471,23 +559,28 @@ __device__ __forceinline__ void edge_fwd_tile(
   if constexpr (PAIRS && !FULL) fwd_issue_group<H, BF16>(p.PQ, s_next, wr, 0, g, colb, wp0, wq0, dd0);
 }
 
-template <int H, bool BF16, bool BRES_REQ>
+template <int H, bool BF16, bool BRES_REQ, bool ATTR>
 __global__ void __launch_bounds__(256, 2) k_edge_fwd(EdgeFwdArgs p, int ntiles) {
   using C = ECfg<H, BF16>;
-  constexpr bool BRES = BRES_REQ && (BF16 || H <= 128);   // keep this wavefront's slice of W2 in registers?
+  static_assert(!ATTR || (BF16 && C::TM == 64), "edge attributes: bf16 operands, 64-edge tiles");
+  // keep this wavefront's slice of W2 in registers? (not with attributes: their accumulators need the room)
+  constexpr bool BRES = BRES_REQ && (BF16 || H <= 128) && !ATTR;
   extern __shared__ __align__(16) unsigned char smem[];
   int* sc = reinterpret_cast<int*>(smem + C::LDS_BYTES);   // [2][3][TM] per-edge scalars, double buffered
+  unsigned short* atb = reinterpret_cast<unsigned short*>(smem + C::LDS_BYTES + 6 * C::TM * 4);   // [2][ATTR_TILE] (ATTR)
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: tile addresses stay in scalar registers
   const int wr = wave / C::WC, wc = wave % C::WC;
   const int x = lane & 31;
   const int E = (int)p.E;
   float w1d[C::CB], b2[C::CB];
+  bf16x8_t bW1a[C::CB];
 #pragma unroll
   for (int j = 0; j < C::CB; ++j) {
     const int n = (wc * C::CB + j) * 32 + x;
-    w1d[j] = p.w1d[n];
+    w1d[j] = ATTR ? 0.f : p.w1d[n];
     b2[j] = p.b2[n];
+    if constexpr (ATTR) bW1a[j] = attr_weight_operand(p.W1a, p.k, H, n, lane);
   }
   typename BFrag<H, BF16>::type breg[BRES ? BFrag<H, BF16>::NKB : 1][C::CB];
   if constexpr (BRES) load_b_resident<H, BF16>(p.W2p, wc, lane, breg);
@@ -495,6 +588,7 @@ __global__ void __launch_bounds__(256, 2) k_edge_fwd(EdgeFwdArgs p, int ntiles) 
   {
     const int s0 = fetch_edge_scalar<C::TM, 3>(p.dst, p.col, p.d2, nullptr, tr.first, tr.end, E, tid);
     if (tid < 3 * C::TM) sc[tid] = s0;
+    if constexpr (ATTR) store_attr4(atb, tid, fetch_attr4(p.attr, p.k, tr.first, tr.end, E, tid));
   }
   __syncthreads();
   unsigned wp0[8], wq0[8];   // bf16 pairs: gathers of the coming tile's first group (see edge_fwd_tile)
@@ -505,12 +599,18 @@ __global__ void __launch_bounds__(256, 2) k_edge_fwd(EdgeFwdArgs p, int ntiles) 
   for (int tile = tr.first; tile < tr.end; tile += tr.step, buf ^= 1) {
     // the next tile's scalars travel while this tile is processed
     const int nxt = fetch_edge_scalar<C::TM, 3>(p.dst, p.col, p.d2, nullptr, tile + tr.step, tr.end, E, tid);
+    uint2 nxa = make_uint2(0u, 0u);
+    if constexpr (ATTR) nxa = fetch_attr4(p.attr, p.k, tile + tr.step, tr.end, E, tid);
     const int* s = sc + buf * 3 * C::TM;
     int* s_next = sc + (buf ^ 1) * 3 * C::TM;
+    const unsigned short* at = atb + buf * ATTR_TILE;
+    unsigned short* at_next = atb + (buf ^ 1) * ATTR_TILE;
     if ((tile + 1) * C::TM <= E)
-      edge_fwd_tile<H, BF16, BRES, true>(p, smem, s, s_next, nxt, tile, E, tid, wr, wc, lane, w1d, b2, breg, wp0, wq0, dd0);
+      edge_fwd_tile<H, BF16, BRES, true, ATTR>(p, smem, s, s_next, nxt, tile, E, tid, wr, wc, lane, w1d, b2, breg, wp0, wq0,
+                                               dd0, at, at_next, nxa, bW1a);
     else
-      edge_fwd_tile<H, BF16, BRES, false>(p, smem, s, s_next, nxt, tile, E, tid, wr, wc, lane, w1d, b2, breg, wp0, wq0, dd0);
+      edge_fwd_tile<H, BF16, BRES, false, ATTR>(p, smem, s, s_next, nxt, tile, E, tid, wr, wc, lane, w1d, b2, breg, wp0, wq0,
+                                                dd0, at, at_next, nxa, bW1a);
   }
 }
 
@@ -526,21 +626,22 @@ static int resident_per_cu(const void* kernel, size_t dyn_lds, int fallback) {
   return n > 8 ? 8 : n;
 }
 
-template <int H, bool BF16>
+template <int H, bool BF16, bool ATTR>
 static int32_t launch_edge_fwd_t(hipStream_t st, const EdgeFwdArgs& a) {
   using C = ECfg<H, BF16>;
   const int64_t ntiles = (a.E + C::TM - 1) / C::TM;
   if (ntiles <= 0) return HGNN_OK;
+  constexpr size_t lds = C::LDS_BYTES + 6 * C::TM * 4 + (ATTR ? 2 * ATTR_TILE * 2 : 0);
   static int per_cu = 0;
   if (!per_cu) {
-    HGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_edge_fwd<H, BF16, true>),
-                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)(C::LDS_BYTES + 6 * C::TM * 4)));
-    per_cu = resident_per_cu(reinterpret_cast<const void*>(&k_edge_fwd<H, BF16, true>), C::LDS_BYTES + 6 * C::TM * 4, 2);
+    HGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_edge_fwd<H, BF16, true, ATTR>),
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    per_cu = resident_per_cu(reinterpret_cast<const void*>(&k_edge_fwd<H, BF16, true, ATTR>), lds, 2);
   }
   int64_t grid = (int64_t)num_cus() * per_cu;
   if (grid > ntiles) grid = ntiles;
   ProfScope ps(PT_EDGE_FUSED_FWD, st);
-  k_edge_fwd<H, BF16, true><<<dim3((unsigned)grid), 256, C::LDS_BYTES + 6 * C::TM * 4, st>>>(a, (int)ntiles);
+  k_edge_fwd<H, BF16, true, ATTR><<<dim3((unsigned)grid), 256, lds, st>>>(a, (int)ntiles);
   HGNN_LAUNCH_CHECK("k_edge_fwd");
   return HGNN_OK;
 }
@@ -548,10 +649,20 @@ static int32_t launch_edge_fwd_t(hipStream_t st, const EdgeFwdArgs& a) {
 int32_t launch_edge_fwd(hipStream_t st, int H, bool bf16, const EdgeFwdArgs& a) {
   HGNN_REQUIRE(a.E >= 0 && a.E <= EDGE_MAX_E, HGNN_ERR_BAD_SHAPE, "edge kernels index edges with 32 bits (E = %lld)",
                (long long)a.E);
+  if (a.k > 1) {
+    HGNN_REQUIRE(bf16 && a.k <= ATTR_K && a.W1a && (a.attr || a.E == 0), HGNN_ERR_BAD_SHAPE,
+                 "edge attributes on the fused kernels: bf16 operands, 2 <= k <= %d", ATTR_K);
+    switch (H) {
+      case 64: return launch_edge_fwd_t<64, true, true>(st, a);
+      case 128: return launch_edge_fwd_t<128, true, true>(st, a);
+      case 256: return launch_edge_fwd_t<256, true, true>(st, a);
+    }
+    return set_error(HGNN_ERR_BAD_SHAPE, "H must be 64, 128 or 256 (got %d)", H);
+  }
   switch (H) {
-    case 64: return bf16 ? launch_edge_fwd_t<64, true>(st, a) : launch_edge_fwd_t<64, false>(st, a);
-    case 128: return bf16 ? launch_edge_fwd_t<128, true>(st, a) : launch_edge_fwd_t<128, false>(st, a);
-    case 256: return bf16 ? launch_edge_fwd_t<256, true>(st, a) : launch_edge_fwd_t<256, false>(st, a);
+    case 64: return bf16 ? launch_edge_fwd_t<64, true, false>(st, a) : launch_edge_fwd_t<64, false, false>(st, a);
+    case 128: return bf16 ? launch_edge_fwd_t<128, true, false>(st, a) : launch_edge_fwd_t<128, false, false>(st, a);
+    case 256: return bf16 ? launch_edge_fwd_t<256, true, false>(st, a) : launch_edge_fwd_t<256, false, false>(st, a);
   }
   return set_error(HGNN_ERR_BAD_SHAPE, "H must be 64, 128 or 256 (got %d)", H);
 }
@@ -884,6 +995,107 @@ int32_t launch_segsum_vm(hipStream_t st, int H, bool bf16, int N, const int32_t*
   return HGNN_OK;
 }
 
+// A skinny product on the matrix cores: per 64-edge tile the v-major g_z1 (the accumulator mapping: lane <-> column)
+// is copied into a row-major LDS tile, from which two wavefronts read it as the A operand (lane <-> edge) of
+// [32 edges x H] x [H x 16 slots]; the B operands (W1a transposed, bf16) are laid out in LDS once per workgroup.
+template <int H>
+__global__ void __launch_bounds__(256)
+k_gattr_vm(int E, const void* __restrict__ X, const float* __restrict__ W1a, int k, float* __restrict__ g_attr) {
+  using C = ECfg<H, true>;
+  constexpr bool PAIRS = H == 256;
+  constexpr int NKB = H / 16;
+  __shared__ __align__(16) unsigned short tile[C::TM * C::STRIDE];
+  __shared__ __align__(16) unsigned short bpk[NKB * 64 * 8];   // operand order: [k step][lane][8]
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wr = wave / C::WC, wc = wave % C::WC;
+  const int g = lane >> 5, x = lane & 31;
+  // B[k = column][n = slot]: lane (n, half) of step kb holds W1a[n][16 kb + 8 half + 0..7]
+  for (int idx = tid; idx < NKB * 64; idx += 256) {
+    const int kb = idx >> 6, l = idx & 63;
+    const int n = l & 31, c0 = kb * 16 + (l >> 5) * 8;
+#pragma unroll
+    for (int t = 0; t < 8; ++t) bpk[idx * 8 + t] = n < k ? (unsigned short)f2bf_bits(W1a[(size_t)n * H + c0 + t]) : 0;
+  }
+  const int ntiles = (E + C::TM - 1) / C::TM;
+  for (int t = blockIdx.x; t < ntiles; t += gridDim.x) {
+    __syncthreads();   // the previous tile has been read (first trip: bpk is complete)
+    // ---- v-major -> row-major: this wavefront's blocks, as the fused kernels hold them
+#pragma unroll
+    for (int i = 0; i < C::RB; ++i) {
+      const int rblk = wr * C::RB + i;
+      const int eb = t * (C::TM / 32) + rblk;
+      if (eb * 32 >= E) {   // rows beyond the last edge: zeros
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+#pragma unroll
+          for (int j = 0; j < C::CB; ++j)
+            tile[(rblk * 32 + 8 * (v >> 2) + 4 * g + (v & 3)) * C::STRIDE + (wc * C::CB + j) * 32 + x] = 0;
+        continue;
+      }
+      if constexpr (PAIRS) {
+        const char* zp = uoff(X, ((size_t)eb * (C::NCB / 2) + wc) * 16 * 256);
+        unsigned w[16];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) w[v] = ldg_nt<unsigned>(zp, lane * 4u + v * 256u);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int row = rblk * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
+          tile[row * C::STRIDE + (wc * 2) * 32 + x] = (unsigned short)(w[v] & 0xffffu);
+          tile[row * C::STRIDE + (wc * 2 + 1) * 32 + x] = (unsigned short)(w[v] >> 16);
+        }
+      } else {
+#pragma unroll
+        for (int j = 0; j < C::CB; ++j) {
+          const int cblk = wc * C::CB + j;
+          const char* zp = uoff(X, (((size_t)eb * C::NCB + cblk) * 16) * 64 * 2);
+          unsigned short w[16];
+#pragma unroll
+          for (int v = 0; v < 16; ++v) w[v] = ldg_nt<unsigned short>(zp, lane * 2u + v * 128u);
+#pragma unroll
+          for (int v = 0; v < 16; ++v) tile[(rblk * 32 + 8 * (v >> 2) + 4 * g + (v & 3)) * C::STRIDE + cblk * 32 + x] = w[v];
+        }
+      }
+    }
+    __syncthreads();
+    // ---- two wavefronts, one 32-edge block each
+    if (wave < C::TM / 32) {
+      f32x16_t acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
+      for (int kb = 0; kb < NKB; ++kb) {
+        const bf16x8_t a = *reinterpret_cast<const bf16x8_t*>(&tile[(wave * 32 + x) * C::STRIDE + kb * 16 + g * 8]);
+        const bf16x8_t b = *reinterpret_cast<const bf16x8_t*>(&bpk[(kb * 64 + lane) * 8]);
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc, 0, 0, 0);
+      }
+      // D: lane (slot x, half g), register v <-> edge 8*(v>>2) + 4g + (v&3) of the block
+      if (x < k) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int e = t * C::TM + wave * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
+          if (e < E) g_attr[(size_t)e * k + x] = acc[v];
+        }
+      }
+    }
+  }
+}
+
+int32_t launch_gattr_vm(hipStream_t st, int H, int64_t E, const void* X_vm, const float* W1a, int k, float* g_attr) {
+  if (E <= 0) return HGNN_OK;
+  HGNN_REQUIRE(k >= 2 && k <= 16 && E <= EDGE_MAX_E, HGNN_ERR_BAD_SHAPE, "gattr: bad k or E");
+  ProfScope ps(PT_MISC, st);
+  int64_t grid = (int64_t)num_cus() * 4;
+  const int64_t ntiles = (E + 63) / 64;
+  if (grid > ntiles) grid = ntiles;
+  switch (H) {
+    case 64: k_gattr_vm<64><<<(unsigned)grid, 256, 0, st>>>((int)E, X_vm, W1a, k, g_attr); break;
+    case 128: k_gattr_vm<128><<<(unsigned)grid, 256, 0, st>>>((int)E, X_vm, W1a, k, g_attr); break;
+    case 256: k_gattr_vm<256><<<(unsigned)grid, 256, 0, st>>>((int)E, X_vm, W1a, k, g_attr); break;
+    default: return set_error(HGNN_ERR_BAD_SHAPE, "H must be 64, 128 or 256");
+  }
+  HGNN_LAUNCH_CHECK("k_gattr_vm");
+  return HGNN_OK;
+}
+
 // ---------------------------------------------------------------------------------------------
 // backward
 // ---------------------------------------------------------------------------------------------
@@ -905,12 +1117,18 @@ int32_t launch_edge_cvec(hipStream_t st, int64_t E, const int32_t* dst, const fl
 }
 
 // One tile of the reverse kernel. FULL: all TM edges of the tile exist (no masking anywhere).
-template <int H, bool BF16, bool FULL>
+// ATTR: k > 1 edge attributes take the place of d2 (at / att: this tile's attributes in LDS, edge-major and
+// slot-major; *_next / nxa: where and what to store for the next tile; bW1a: the attribute weights as matrix-core
+// operands; gacc: running g_W1a of this wavefront's columns, slots in the accumulator rows).
+template <int H, bool BF16, bool FULL, bool ATTR>
 __device__ __forceinline__ void edge_bwd_tile(const EdgeBwdArgs& p, unsigned char* smem, const int* s, int* s_next,
                                               int nxt, int tile, int E, int tid, int wr, int wc, int lane,
                                               const float (&w1d)[ECfg<H, BF16>::CB], const float (&wxn)[ECfg<H, BF16>::CB],
                                               float (&sb2)[ECfg<H, BF16>::CB], float (&swx)[ECfg<H, BF16>::CB],
-                                              float (&sw1)[ECfg<H, BF16>::CB]) {
+                                              float (&sw1)[ECfg<H, BF16>::CB], const unsigned short* at,
+                                              const unsigned short* att, unsigned short* at_next, unsigned short* att_next,
+                                              uint2 nxa, const bf16x8_t (&bW1a)[ECfg<H, BF16>::CB],
+                                              f32x16_t (&gacc)[ECfg<H, BF16>::CB]) {
   using C = ECfg<H, BF16>;
   constexpr bool PAIRS = BF16 && C::CB == 2;
   constexpr unsigned GM_ROW = PAIRS ? H * 2u : 2u * H * 4u;   // row pitch of g_M in bytes (checked by the launcher)
@@ -1031,7 +1249,12 @@ __device__ __forceinline__ void edge_bwd_tile(const EdgeBwdArgs& p, unsigned cha
   f32x16_t acc[C::RB][C::CB];
   tile_mma<H, BF16>(smem, p.W2Tp, wr, wc, lane, acc);
   s_next[tid] = nxt;
+  if constexpr (ATTR) {
+    store_attr4(at_next, tid, nxa);
+    store_attr4_t(att_next, tid, nxa);
+  }
   __syncthreads();
+  f32x16_t zat[C::CB];   // ATTR: attribute term of z1 of the 32-edge block at hand
   // ---- g_z1 = g_a1 * silu'(z1), z1 recomputed from the projected node features
   if constexpr (PAIRS && FULL) {
     // the same pipelining; d2 is read from LDS when it is used so that only the gathered words live twice
@@ -1058,20 +1281,38 @@ __device__ __forceinline__ void edge_bwd_tile(const EdgeBwdArgs& p, unsigned cha
       const int rblk = wr * C::RB + i;
       const int eb = tile * (C::TM / 32) + rblk;
       float dd[8];
-      lds_rows8(s + 2 * C::TM, rblk, vh, g, dd);
+      if constexpr (!ATTR) lds_rows8(s + 2 * C::TM, rblk, vh, g, dd);
+      if constexpr (ATTR) {
+        if (vh == 0) attr_z1_block<C::CB>(at, rblk, lane, bW1a, zat);
+      }
       char* o = uoff(p.gz1_vm, (((size_t)eb * (C::NCB / 2) + wc) * 16 + 8 * vh) * 256);
+      float ga[2][8];
 #pragma unroll
       for (int u = 0; u < 8; ++u) {
-        const float z0 = __uint_as_float(wp[sl][u] << 16) + __uint_as_float(wq[sl][u] << 16) + dd[u] * w1d[0];
-        const float z1 = __uint_as_float(wp[sl][u] & 0xffff0000u) + __uint_as_float(wq[sl][u] & 0xffff0000u) + dd[u] * w1d[1];
+        const float t0 = ATTR ? zat[0][8 * vh + u] : dd[u] * w1d[0];
+        const float t1 = ATTR ? zat[1][8 * vh + u] : dd[u] * w1d[1];
+        const float z0 = __uint_as_float(wp[sl][u] << 16) + __uint_as_float(wq[sl][u] << 16) + t0;
+        const float z1 = __uint_as_float(wp[sl][u] & 0xffff0000u) + __uint_as_float(wq[sl][u] & 0xffff0000u) + t1;
         const float g0 = acc[i][0][8 * vh + u] * dsilu_f(z0);
         const float g1 = acc[i][1][8 * vh + u] * dsilu_f(z1);
-        sw1[0] += dd[u] * g0;
-        sw1[1] += dd[u] * g1;
+        if constexpr (ATTR) {
+          ga[0][u] = g0;
+          ga[1][u] = g1;
+        } else {
+          sw1[0] += dd[u] * g0;
+          sw1[1] += dd[u] * g1;
+        }
         stg_nt<unsigned>(o, lane * 4u + u * 256u, pack_bf16x2(g0, g1));
       }
+      if constexpr (ATTR) {
+        const bf16x8_t aT = attr_t_operand(att, rblk, vh, lane);
 #pragma unroll
-      for (int j = 0; j < C::CB; ++j) asm volatile("" : "+v"(sw1[j]));
+        for (int j = 0; j < C::CB; ++j)
+          gacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aT, pack_operand8(ga[j]), gacc[j], 0, 0, 0);
+      } else {
+#pragma unroll
+        for (int j = 0; j < C::CB; ++j) asm volatile("" : "+v"(sw1[j]));
+      }
     }
   } else
 #pragma unroll
@@ -1088,14 +1329,24 @@ __device__ __forceinline__ void edge_bwd_tile(const EdgeBwdArgs& p, unsigned cha
       lds_rows8(s + 2 * C::TM, rblk, vh, g, dd);
       float z[C::CB][8];
       gather_z1<H, C::CB, PAIRS>(p.PQ, di, ci, dd, w1d, colb, z);
+      if constexpr (ATTR) {
+        if (vh == 0) attr_z1_block<C::CB>(at, rblk, lane, bW1a, zat);
+      }
       float gv[C::CB][8];
 #pragma unroll
       for (int j = 0; j < C::CB; ++j)
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
-          gv[j][u] = acc[i][j][8 * vh + u] * dsilu_f(z[j][u]);   // rows beyond E have acc == 0
-          sw1[j] += dd[u] * gv[j][u];
+          const float zz = ATTR ? z[j][u] + zat[j][8 * vh + u] : z[j][u];
+          gv[j][u] = acc[i][j][8 * vh + u] * dsilu_f(zz);   // rows beyond E have acc == 0
+          if constexpr (!ATTR) sw1[j] += dd[u] * gv[j][u];
         }
+      if constexpr (ATTR) {
+        const bf16x8_t aT = attr_t_operand(att, rblk, vh, lane);
+#pragma unroll
+        for (int j = 0; j < C::CB; ++j)
+          gacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aT, pack_operand8(gv[j]), gacc[j], 0, 0, 0);
+      }
       if constexpr (PAIRS) {
         char* o = uoff(p.gz1_vm, (((size_t)eb * (C::NCB / 2) + wc) * 16 + 8 * vh) * 256);
 #pragma unroll
@@ -1125,11 +1376,15 @@ __device__ __forceinline__ void edge_bwd_tile(const EdgeBwdArgs& p, unsigned cha
   }
 }
 
-template <int H, bool BF16>
-__global__ void __launch_bounds__(256, 3) k_edge_bwd(EdgeBwdArgs p, int ntiles) {
+template <int H, bool BF16, bool ATTR>
+__global__ void __launch_bounds__(256, ATTR ? 2 : 3) k_edge_bwd(EdgeBwdArgs p, int ntiles) {
   using C = ECfg<H, BF16>;
+  static_assert(!ATTR || (BF16 && C::TM == 64), "edge attributes: bf16 operands, 64-edge tiles");
   extern __shared__ __align__(16) unsigned char smem[];
   int* sc = reinterpret_cast<int*>(smem + C::LDS_BYTES);   // [2][4][TM] per-edge scalars dst|col|d2|c, double buffered
+  // ATTR: [2][ATTR_TILE] attributes edge-major, then [2][ATTR_T_TILE] slot-major
+  unsigned short* atb = reinterpret_cast<unsigned short*>(smem + C::LDS_BYTES + 8 * C::TM * 4);
+  unsigned short* attb = atb + 2 * ATTR_TILE;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: tile addresses stay in scalar registers
   const int wr = wave / C::WC, wc = wave % C::WC;
@@ -1137,26 +1392,46 @@ __global__ void __launch_bounds__(256, 3) k_edge_bwd(EdgeBwdArgs p, int ntiles) 
   const int E = (int)p.E;
   static_assert(4 * C::TM == 256, "one per-edge scalar per thread");
   float w1d[C::CB], wxn[C::CB], sb2[C::CB], swx[C::CB], sw1[C::CB];
+  bf16x8_t bW1a[C::CB];
+  f32x16_t gacc[C::CB];
 #pragma unroll
   for (int j = 0; j < C::CB; ++j) {
     const int n = (wc * C::CB + j) * 32 + x;
-    w1d[j] = p.w1d[n];
+    w1d[j] = ATTR ? 0.f : p.w1d[n];
     wxn[j] = p.wx[n];
     sb2[j] = swx[j] = sw1[j] = 0.f;
+    if constexpr (ATTR) {
+      bW1a[j] = attr_weight_operand(p.W1a, p.k, H, n, lane);
+#pragma unroll
+      for (int v = 0; v < 16; ++v) gacc[j][v] = 0.f;
+    }
   }
   const TileRange tr = xcd_tile_range(ntiles);
   sc[tid] = fetch_edge_scalar<C::TM, 4>(p.dst, p.col, p.d2, p.cvec, tr.first, tr.end, E, tid);
+  if constexpr (ATTR) {
+    const uint2 a0 = fetch_attr4(p.attr, p.k, tr.first, tr.end, E, tid);
+    store_attr4(atb, tid, a0);
+    store_attr4_t(attb, tid, a0);
+  }
   __syncthreads();
   int buf = 0;
   for (int tile = tr.first; tile < tr.end; tile += tr.step, buf ^= 1) {
     // the next tile's scalars travel while this tile is processed
     const int nxt = fetch_edge_scalar<C::TM, 4>(p.dst, p.col, p.d2, p.cvec, tile + tr.step, tr.end, E, tid);
+    uint2 nxa = make_uint2(0u, 0u);
+    if constexpr (ATTR) nxa = fetch_attr4(p.attr, p.k, tile + tr.step, tr.end, E, tid);
     const int* s = sc + buf * 4 * C::TM;
     int* s_next = sc + (buf ^ 1) * 4 * C::TM;
+    const unsigned short* at = atb + buf * ATTR_TILE;
+    const unsigned short* att = attb + buf * ATTR_T_TILE;
+    unsigned short* at_next = atb + (buf ^ 1) * ATTR_TILE;
+    unsigned short* att_next = attb + (buf ^ 1) * ATTR_T_TILE;
     if ((tile + 1) * C::TM <= E)
-      edge_bwd_tile<H, BF16, true>(p, smem, s, s_next, nxt, tile, E, tid, wr, wc, lane, w1d, wxn, sb2, swx, sw1);
+      edge_bwd_tile<H, BF16, true, ATTR>(p, smem, s, s_next, nxt, tile, E, tid, wr, wc, lane, w1d, wxn, sb2, swx, sw1, at, att,
+                                         at_next, att_next, nxa, bW1a, gacc);
     else
-      edge_bwd_tile<H, BF16, false>(p, smem, s, s_next, nxt, tile, E, tid, wr, wc, lane, w1d, wxn, sb2, swx, sw1);
+      edge_bwd_tile<H, BF16, false, ATTR>(p, smem, s, s_next, nxt, tile, E, tid, wr, wc, lane, w1d, wxn, sb2, swx, sw1, at, att,
+                                          at_next, att_next, nxa, bW1a, gacc);
   }
   // ---- per-column partial sums of this wavefront: combine the two lane halves, one writer per column
 #pragma unroll
@@ -1164,28 +1439,39 @@ __global__ void __launch_bounds__(256, 3) k_edge_bwd(EdgeBwdArgs p, int ntiles) 
     const float a = sb2[j] + __shfl_xor(sb2[j], 32);
     const float b = swx[j] + __shfl_xor(swx[j], 32);
     const float c = sw1[j] + __shfl_xor(sw1[j], 32);
+    const int n = (wc * C::CB + j) * 32 + x;
     if (g == 0) {
-      const int n = (wc * C::CB + j) * 32 + x;
       float* o = p.colpart + ((size_t)(blockIdx.x * C::WR + wr) * 3) * H + n;
       o[0] = a;
       o[H] = b;
       o[2 * H] = c;
+    }
+    if constexpr (ATTR) {
+      // accumulator row 8*(v>>2) + 4g + (v&3) is attribute slot m; slots 0..15 sit in registers 0..7
+      float* o = p.attrpart + (size_t)(blockIdx.x * C::WR + wr) * p.k * H + n;
+#pragma unroll
+      for (int v = 0; v < 8; ++v) {
+        const int m = 8 * (v >> 2) + 4 * g + (v & 3);
+        if (m < p.k) o[(size_t)m * H] = gacc[j][v];
+      }
     }
   }
 }
 
 constexpr int EDGE_BWD_MAX_GRID = 2048;
 size_t edge_bwd_colpart_floats(int H) { return (size_t)EDGE_BWD_MAX_GRID * 2 * 3 * H; }
+size_t edge_bwd_attrpart_floats(int H) { return (size_t)EDGE_BWD_MAX_GRID * 2 * ATTR_K * H; }
 
-template <int H, bool BF16>
+template <int H, bool BF16, bool ATTR>
 static int32_t launch_edge_bwd_t(hipStream_t st, const EdgeBwdArgs& a) {
   using C = ECfg<H, BF16>;
   const int64_t ntiles = (a.E + C::TM - 1) / C::TM;
+  constexpr size_t lds = C::LDS_BYTES + 8 * C::TM * 4 + (ATTR ? 2 * (ATTR_TILE + ATTR_T_TILE) * 2 : 0);
   static int per_cu = 0;
   if (!per_cu) {
-    HGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_edge_bwd<H, BF16>),
-                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)(C::LDS_BYTES + 8 * C::TM * 4)));
-    per_cu = resident_per_cu(reinterpret_cast<const void*>(&k_edge_bwd<H, BF16>), C::LDS_BYTES + 8 * C::TM * 4, 3);
+    HGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_edge_bwd<H, BF16, ATTR>),
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    per_cu = resident_per_cu(reinterpret_cast<const void*>(&k_edge_bwd<H, BF16, ATTR>), lds, ATTR ? 2 : 3);
   }
   int64_t grid = (int64_t)num_cus() * per_cu;
   if (grid > EDGE_BWD_MAX_GRID) grid = EDGE_BWD_MAX_GRID;
@@ -1193,11 +1479,16 @@ static int32_t launch_edge_bwd_t(hipStream_t st, const EdgeBwdArgs& a) {
   if (grid < 1) grid = 1;  // E == 0: one block writes zero partials
   {
     ProfScope ps(PT_EDGE_FUSED_BWD, st);
-    k_edge_bwd<H, BF16><<<dim3((unsigned)grid), 256, C::LDS_BYTES + 8 * C::TM * 4, st>>>(a, (int)ntiles);
+    k_edge_bwd<H, BF16, ATTR><<<dim3((unsigned)grid), 256, lds, st>>>(a, (int)ntiles);
     HGNN_LAUNCH_CHECK("k_edge_bwd");
   }
   float* dest[4] = {a.g_b2, a.g_wx, a.g_w1d, nullptr};
-  return launch_reduce_partials(st, a.colpart, (int)grid * C::WR, 3, H, dest, 1, 0);
+  HGNN_TRY(launch_reduce_partials(st, a.colpart, (int)grid * C::WR, 3, H, dest, 1, 0));
+  if (ATTR) {
+    float* adest[4] = {a.g_W1a, nullptr, nullptr, nullptr};
+    HGNN_TRY(launch_reduce_partials(st, a.attrpart, (int)grid * C::WR, 1, (long)a.k * H, adest, 1, 0));
+  }
+  return HGNN_OK;
 }
 
 int32_t launch_edge_bwd(hipStream_t st, int H, bool bf16, const EdgeBwdArgs& a) {
@@ -1205,10 +1496,20 @@ int32_t launch_edge_bwd(hipStream_t st, int H, bool bf16, const EdgeBwdArgs& a) 
                (long long)a.E);
   HGNN_REQUIRE(a.ldgM == (edge_pairs(H, bf16) ? H / 2 : 2 * H), HGNN_ERR_BAD_SHAPE,
                "g_M must be the second half of a [N,2H] tensor, or [N,H/2] words of bf16 pairs");
+  if (a.k > 1) {
+    HGNN_REQUIRE(bf16 && a.k <= ATTR_K && a.W1a && a.attrpart && a.g_W1a && (a.attr || a.E == 0), HGNN_ERR_BAD_SHAPE,
+                 "edge attributes on the fused kernels: bf16 operands, 2 <= k <= %d", ATTR_K);
+    switch (H) {
+      case 64: return launch_edge_bwd_t<64, true, true>(st, a);
+      case 128: return launch_edge_bwd_t<128, true, true>(st, a);
+      case 256: return launch_edge_bwd_t<256, true, true>(st, a);
+    }
+    return set_error(HGNN_ERR_BAD_SHAPE, "H must be 64, 128 or 256 (got %d)", H);
+  }
   switch (H) {
-    case 64: return bf16 ? launch_edge_bwd_t<64, true>(st, a) : launch_edge_bwd_t<64, false>(st, a);
-    case 128: return bf16 ? launch_edge_bwd_t<128, true>(st, a) : launch_edge_bwd_t<128, false>(st, a);
-    case 256: return bf16 ? launch_edge_bwd_t<256, true>(st, a) : launch_edge_bwd_t<256, false>(st, a);
+    case 64: return bf16 ? launch_edge_bwd_t<64, true, false>(st, a) : launch_edge_bwd_t<64, false, false>(st, a);
+    case 128: return bf16 ? launch_edge_bwd_t<128, true, false>(st, a) : launch_edge_bwd_t<128, false, false>(st, a);
+    case 256: return bf16 ? launch_edge_bwd_t<256, true, false>(st, a) : launch_edge_bwd_t<256, false, false>(st, a);
   }
   return set_error(HGNN_ERR_BAD_SHAPE, "H must be 64, 128 or 256 (got %d)", H);
 }

@@ -16,11 +16,11 @@
 
 namespace hgnn {
 
-struct LayerOff {  // element offsets into the flat weight buffer
+struct LayerOff {  // element offsets into the flat weight buffer (k edge attributes: W1 has 2H + k rows)
   long W1, b1, W2, b2, wx, W3, b3, W4, b4, total;
-  explicit LayerOff(long H) {
+  explicit LayerOff(long H, long k = 1) {
     long o = 0;
-    W1 = o; o += (2 * H + 1) * H;
+    W1 = o; o += (2 * H + k) * H;
     b1 = o; o += H;
     W2 = o; o += H * H;
     b2 = o; o += H;
@@ -36,21 +36,24 @@ struct LayerOff {  // element offsets into the flat weight buffer
 struct LayerSaved {
   float* PQ;    // [N,2H] fp32  P = h W1a + b1 | Q = h W1b   (or the same as bf16 pairs, [N,H] words)
   void* z2_vm;  // [E32,H] z2, v-major fragment order (bf16 or fp32)
-  void* a1_pk;  // [E32,H] silu(z1), operand-packed fragment order (bf16 or fp32); null with bf16 pairs, where the
-                // reverse pass recomputes it
+  void* a1_pk;  // [E32,H] silu(z1), operand-packed fragment order (bf16 or fp32); null with bf16 pairs and the single
+                // d2 attribute, where the reverse pass recomputes it
   float* M;     // [N,H]
   float* z3;    // [N,H]
   float* xe;    // [E] x_e = wx . m_e (written only when the caller may ask for edge gradients)
   size_t bytes;
 };
 
-static LayerSaved carve_saved(void* p, int N, int64_t E, int H, bool bf16) {
+// a1 is recomputed (not stored) where the weight-gradient kernel can rebuild it from the gathers alone
+static bool a1_recomputed(int H, bool bf16, int k) { return edge_pairs(H, bf16) && k == 1; }
+
+static LayerSaved carve_saved(void* p, int N, int64_t E, int H, bool bf16, int k = 1) {
   Carver c(p);
   LayerSaved s;
   const size_t eb = frag_rows(E) * H * (bf16 ? 2 : 4);
   s.PQ = c.take<float>((size_t)N * 2 * H);
   s.z2_vm = c.take<char>(eb);
-  s.a1_pk = edge_pairs(H, bf16) ? nullptr : c.take<char>(eb);
+  s.a1_pk = a1_recomputed(H, bf16, k) ? nullptr : c.take<char>(eb);
   s.M = c.take<float>((size_t)N * H);
   s.z3 = c.take<float>((size_t)N * H);
   s.xe = c.take<float>((size_t)E + 4);
@@ -70,10 +73,11 @@ struct LayerWs {
   float* partial;  // split-K / column-sum partials of the main stream
   float* partial2; // the same for the work that runs on the side stream
   float* cs_partial;  // column-sum partials of the node weight-gradient kernel (side stream)
+  float* attrpart;    // partials of the attribute rows of g_W1 (k > 1 only)
   size_t bytes;
 };
 
-static LayerWs carve_ws(void* p, int N, int64_t E, int H, bool bf16) {
+static LayerWs carve_ws(void* p, int N, int64_t E, int H, bool bf16, int k = 1) {
   Carver c(p);
   LayerWs w;
   w.packed = c.take<char>(6 * packed_block_bytes(H, bf16));
@@ -90,6 +94,7 @@ static LayerWs carve_ws(void* p, int N, int64_t E, int H, bool bf16) {
   w.partial = c.take<float>(pf);
   w.partial2 = c.take<float>(pf);
   w.cs_partial = c.take<float>(wgrad_colsum_partial_floats(H, N));
+  w.attrpart = k > 1 ? c.take<float>(edge_bwd_attrpart_floats(H)) : nullptr;
   w.bytes = c.used();
   return w;
 }
@@ -146,32 +151,38 @@ extern "C" int32_t hgnn_set_side_stream(int32_t enable) {
   return before;
 }
 
-extern "C" int32_t hgnn_mp_layer_workspace_bytes(int32_t N, int64_t E, int32_t H, int32_t dtype,
-                                                 size_t* ws_bytes_host, size_t* saved_bytes_host) {
+static int32_t layer_sizes(int32_t N, int64_t E, int32_t H, int32_t k, int32_t dtype, size_t* ws_bytes_host,
+                           size_t* saved_bytes_host) {
   HGNN_TRY(check_layer_args(N, E, H, dtype));
   HGNN_REQUIRE(ws_bytes_host && saved_bytes_host, HGNN_ERR_NULLPTR, "null size pointer");
   if (wide_H(H)) {
-    wide_layer_sizes(N, E, H, 1, ws_bytes_host, saved_bytes_host);
+    wide_layer_sizes(N, E, H, k, ws_bytes_host, saved_bytes_host);
     return HGNN_OK;
   }
-  *ws_bytes_host = carve_ws(nullptr, N, E, H, dtype == HGNN_BF16).bytes;
-  *saved_bytes_host = carve_saved(nullptr, N, E, H, dtype == HGNN_BF16).bytes;
+  *ws_bytes_host = carve_ws(nullptr, N, E, H, dtype == HGNN_BF16, k).bytes;
+  *saved_bytes_host = carve_saved(nullptr, N, E, H, dtype == HGNN_BF16, k).bytes;
   return HGNN_OK;
 }
 
+extern "C" int32_t hgnn_mp_layer_workspace_bytes(int32_t N, int64_t E, int32_t H, int32_t dtype,
+                                                 size_t* ws_bytes_host, size_t* saved_bytes_host) {
+  return layer_sizes(N, E, H, 1, dtype, ws_bytes_host, saved_bytes_host);
+}
+
 // Scratch behind the workspace proper for calls without a saved buffer: the saved tensors and two [N,3] vectors
-static size_t unsaved_extra_bytes(int N, int64_t E, int H, bool bf16) {
-  return carve_saved(nullptr, N, E, H, bf16).bytes + 2 * align_up((size_t)N * 3 * sizeof(float));
+static size_t unsaved_extra_bytes(int N, int64_t E, int H, bool bf16, int k) {
+  return carve_saved(nullptr, N, E, H, bf16, k).bytes + 2 * align_up((size_t)N * 3 * sizeof(float));
 }
 
 // Everything of the forward pass that the reverse pass needs again (P|Q, z2 (a1), M, z3), written to `s`; also v_out.
 // Packs its own weight blocks into w.packed: 0 W1a, 1 W1b, 2 W2, 3 W3a, 4 W3b, 5 W4.
 // keep_xe: also keep x_e = wx . m_e per edge (fused kernels only; the fragment path always does)
-static int32_t layer_fwd_core(hipStream_t st, int32_t N, int64_t E, int32_t H, bool bf16, float alpha,
-                              const int32_t* row_ptr, const int32_t* dst, const int32_t* col, const float* d2,
+// k == 1: `attr` is the single per-edge attribute (the squared length); k > 1: [E,k] attributes, bf16 operands
+static int32_t layer_fwd_core(hipStream_t st, int32_t N, int64_t E, int32_t H, int32_t k, bool bf16, float alpha,
+                              const int32_t* row_ptr, const int32_t* dst, const int32_t* col, const float* attr,
                               const float* rvec, const float* h_in, const float* v_in, const float* W, float* v_out,
                               const LayerWs& w, const LayerSaved& s, bool keep_xe) {
-  const LayerOff o(H);
+  const LayerOff o(H, k);
   PackArgs pk;
   pk.src = W;
   pk.dst = w.packed;
@@ -200,7 +211,9 @@ static int32_t layer_fwd_core(hipStream_t st, int32_t N, int64_t E, int32_t H, b
   }
   {  // per edge: a1 = silu(P[dst] + Q[col] + d2*w1d), z2 = a1 W2 + b2   (one fused kernel)
     EdgeFwdArgs e;
-    e.E = E; e.dst = dst; e.col = col; e.d2 = d2;
+    e.E = E; e.dst = dst; e.col = col;
+    if (k > 1) { e.d2 = nullptr; e.attr = attr; e.k = k; e.W1a = W + o.W1 + 2 * HH; }
+    else e.d2 = attr;
     e.PQ = s.PQ; e.w1d = W + o.W1 + 2 * HH;
     e.W2p = static_cast<const char*>(w.packed) + 2 * packed_block_bytes(H, bf16);
     e.b2 = W + o.b2;
@@ -221,7 +234,7 @@ static int32_t layer_fwd_core(hipStream_t st, int32_t N, int64_t E, int32_t H, b
   return HGNN_OK;
 }
 
-static int32_t mp_layer_fwd_impl(void* stream, int32_t N, int64_t E, int32_t H, int32_t dtype, float alpha,
+static int32_t mp_layer_fwd_impl(void* stream, int32_t N, int64_t E, int32_t H, int32_t k, int32_t dtype, float alpha,
                                  const int32_t* row_ptr, const int32_t* dst, const int32_t* col, const float* d2,
                                  const float* rvec, const float* h_in, const float* v_in, const float* W, float* h_out,
                                  float* v_out, void* saved, size_t saved_bytes, void* ws, size_t ws_bytes, bool keep_xe) {
@@ -246,20 +259,20 @@ static int32_t mp_layer_fwd_impl(void* stream, int32_t N, int64_t E, int32_t H, 
     return wide_layer_fwd(st, a);
   }
   const bool bf16 = dtype == HGNN_BF16;
-  LayerWs w = carve_ws(ws, N, E, H, bf16);
+  LayerWs w = carve_ws(ws, N, E, H, bf16, k);
   if (saved == nullptr) {
     // nothing is kept for the reverse pass: the intermediates live behind the workspace proper for this call only
-    const size_t need = w.bytes + unsaved_extra_bytes(N, E, H, bf16);
+    const size_t need = w.bytes + unsaved_extra_bytes(N, E, H, bf16, k);
     HGNN_REQUIRE(ws_bytes >= need, HGNN_ERR_WORKSPACE_TOO_SMALL,
                  "mp_layer workspace without a saved buffer: need %zu bytes (workspace + saved size), got %zu", need, ws_bytes);
     saved = static_cast<char*>(ws) + w.bytes;
     saved_bytes = ws_bytes - w.bytes;
   }
-  LayerSaved s = carve_saved(saved, N, E, H, bf16);
+  LayerSaved s = carve_saved(saved, N, E, H, bf16, k);
   HGNN_REQUIRE(ws_bytes >= w.bytes, HGNN_ERR_WORKSPACE_TOO_SMALL, "mp_layer workspace: need %zu bytes, got %zu", w.bytes, ws_bytes);
   HGNN_REQUIRE(saved_bytes >= s.bytes, HGNN_ERR_WORKSPACE_TOO_SMALL, "mp_layer saved buffer: need %zu bytes, got %zu", s.bytes, saved_bytes);
-  const LayerOff o(H);
-  HGNN_TRY(layer_fwd_core(st, N, E, H, bf16, alpha, row_ptr, dst, col, d2, rvec, h_in, v_in, W, v_out, w, s, keep_xe));
+  const LayerOff o(H, k);
+  HGNN_TRY(layer_fwd_core(st, N, E, H, k, bf16, alpha, row_ptr, dst, col, d2, rvec, h_in, v_in, W, v_out, w, s, keep_xe));
   {  // h' = h + silu(z3) W4 + b4
     GemmArgs g;
     g.A[0] = s.z3; g.lda[0] = H; g.a_silu = 1;
@@ -278,13 +291,13 @@ extern "C" int32_t hgnn_mp_layer_fwd(void* stream, int32_t N, int64_t E, int32_t
                                      const float* d2, const float* rvec, const float* h_in, const float* v_in,
                                      const float* W, float* h_out, float* v_out, void* saved, size_t saved_bytes,
                                      void* ws, size_t ws_bytes) {
-  return mp_layer_fwd_impl(stream, N, E, H, dtype, alpha, row_ptr, dst, col, d2, rvec, h_in, v_in, W, h_out, v_out, saved,
+  return mp_layer_fwd_impl(stream, N, E, H, 1, dtype, alpha, row_ptr, dst, col, d2, rvec, h_in, v_in, W, h_out, v_out, saved,
                            saved_bytes, ws, ws_bytes, false);
 }
 
 // g_d2 / g_rvec (optional, fused kernels): gradient with respect to d2 and to the edge vectors; the forward pass must
 // have kept x_e
-static int32_t mp_layer_bwd_impl(void* stream, int32_t N, int64_t E, int32_t H, int32_t dtype, float alpha,
+static int32_t mp_layer_bwd_impl(void* stream, int32_t N, int64_t E, int32_t H, int32_t k, int32_t dtype, float alpha,
                                  const int32_t* row_ptr, const int32_t* dst, const int32_t* col, const float* d2,
                                  const float* rvec, const int32_t* colT_ptr, const int32_t* permT, const float* h_in,
                                  const float* W, const void* saved, size_t saved_bytes, const float* g_h_out,
@@ -297,7 +310,7 @@ static int32_t mp_layer_bwd_impl(void* stream, int32_t N, int64_t E, int32_t H, 
                HGNN_ERR_NULLPTR, "mp_layer_bwd: null pointer");
   HGNN_REQUIRE(E == 0 || (dst && col && d2 && rvec && permT), HGNN_ERR_NULLPTR, "mp_layer_bwd: null edge array");
   HGNN_REQUIRE(N == 0 || g_h_in != g_h_out, HGNN_ERR_BAD_SHAPE, "g_h_in may not alias g_h_out");
-  if (N == 0) return launch_fill_f32(st, gW, LayerOff(H).total, 0.f);
+  if (N == 0) return launch_fill_f32(st, gW, LayerOff(H, k).total, 0.f);
   if (wide_H(H)) {
     HGNN_REQUIRE(saved != nullptr, HGNN_ERR_UNIMPLEMENTED,
                  "mp_layer_bwd without a saved buffer exists at H = 64, 128, 256 only (H = %d)", H);
@@ -314,27 +327,27 @@ static int32_t mp_layer_bwd_impl(void* stream, int32_t N, int64_t E, int32_t H, 
     return wide_layer_bwd(st, a);
   }
   const bool bf16 = dtype == HGNN_BF16;
-  LayerWs w = carve_ws(ws, N, E, H, bf16);
+  LayerWs w = carve_ws(ws, N, E, H, bf16, k);
   const bool recompute = saved == nullptr;
   if (recompute) {
     HGNN_REQUIRE(g_d2 == nullptr && g_rvec == nullptr, HGNN_ERR_BAD_SHAPE,
                  "edge gradients need the saved buffer of hgnn_mp_layer_attr_fwd");
-    const size_t need = w.bytes + unsaved_extra_bytes(N, E, H, bf16);
+    const size_t need = w.bytes + unsaved_extra_bytes(N, E, H, bf16, k);
     HGNN_REQUIRE(ws_bytes >= need, HGNN_ERR_WORKSPACE_TOO_SMALL,
                  "mp_layer workspace without a saved buffer: need %zu bytes (workspace + saved size), got %zu", need, ws_bytes);
     saved = static_cast<char*>(ws) + w.bytes;
     saved_bytes = ws_bytes - w.bytes;
   }
-  LayerSaved s = carve_saved(const_cast<void*>(saved), N, E, H, bf16);
+  LayerSaved s = carve_saved(const_cast<void*>(saved), N, E, H, bf16, k);
   HGNN_REQUIRE(ws_bytes >= w.bytes, HGNN_ERR_WORKSPACE_TOO_SMALL, "mp_layer workspace: need %zu bytes, got %zu", w.bytes, ws_bytes);
   HGNN_REQUIRE(saved_bytes >= s.bytes, HGNN_ERR_WORKSPACE_TOO_SMALL, "mp_layer saved buffer: need %zu bytes, got %zu", s.bytes, saved_bytes);
-  const LayerOff o(H);
+  const LayerOff o(H, k);
   const long HH = (long)H * H;
   if (recompute) {
     // the forward pass of this layer once more, up to z3 (its v' goes to scratch; the input v does not matter for
     // anything the reverse pass reads, so any valid [N,3] array serves)
     float* v_scratch = reinterpret_cast<float*>(static_cast<char*>(const_cast<void*>(saved)) + s.bytes);
-    HGNN_TRY(layer_fwd_core(st, N, E, H, bf16, alpha, row_ptr, dst, col, d2, rvec, h_in, g_v_out, W, v_scratch, w, s, false));
+    HGNN_TRY(layer_fwd_core(st, N, E, H, k, bf16, alpha, row_ptr, dst, col, d2, rvec, h_in, g_v_out, W, v_scratch, w, s, false));
   }
 
   // transposed blocks: 0 W4^T, 1 W3a^T, 2 W3b^T, 3 W2^T, 4 W1a^T, 5 W1b^T
@@ -404,7 +417,13 @@ static int32_t mp_layer_bwd_impl(void* stream, int32_t N, int64_t E, int32_t H, 
   HGNN_TRY(stream_after(st, sx, ss.ev[5]));
   {
     EdgeBwdArgs e;
-    e.E = E; e.dst = dst; e.col = col; e.d2 = d2;
+    e.E = E; e.dst = dst; e.col = col;
+    if (k > 1) {
+      e.d2 = nullptr; e.attr = d2; e.k = k; e.W1a = W + o.W1 + 2 * HH;
+      e.attrpart = w.attrpart; e.g_W1a = gW + o.W1 + 2 * HH;
+    } else {
+      e.d2 = d2;
+    }
     e.PQ = s.PQ; e.w1d = W + o.W1 + 2 * HH;
     e.W2Tp = static_cast<const char*>(w.packed) + 3 * packed_block_bytes(H, bf16);
     e.z2_vm = s.z2_vm;
@@ -413,19 +432,25 @@ static int32_t mp_layer_bwd_impl(void* stream, int32_t N, int64_t E, int32_t H, 
     e.cvec = w.cvec; e.wx = W + o.wx; e.alpha = alpha;
     e.gz2_pk = w.gz2_pk; e.gz1_vm = w.gz1_vm;
     e.colpart = w.partial;
-    e.g_b2 = gW + o.b2; e.g_wx = gW + o.wx; e.g_w1d = gW + o.W1 + 2 * HH;
+    e.g_b2 = gW + o.b2; e.g_wx = gW + o.wx; e.g_w1d = k > 1 ? nullptr : gW + o.W1 + 2 * HH;
     HGNN_TRY(launch_edge_bwd(st, H, bf16, e));
   }
   HGNN_TRY(stream_after(sx, st, ss.ev[2]));
   // side: g_W2 = a1^T g_z2 streams while the main stream runs the two segment sums
-  if (edge_pairs(H, bf16))
+  if (a1_recomputed(H, bf16, k))
     HGNN_TRY(launch_wgrad_frag_recompute(sx, H, E, dst, col, d2, s.PQ, W + o.W1 + 2 * HH, w.gz2_pk, w.partial2,
                                          gW + o.W2));
   else
     HGNN_TRY(launch_wgrad_frag(sx, H, bf16, E, s.a1_pk, w.gz2_pk, w.partial2, gW + o.W2));
   // g_P (and, on request, the gradient with respect to d2: the dot of every g_z1 row with the d2 row of W1)
-  HGNN_TRY(launch_segsum_vm(st, H, bf16, N, row_ptr, nullptr, w.gz1_vm, w.g_PQ, 2 * H, PT_SEGSUM_DST,
-                            W + o.W1 + 2 * HH, g_d2));
+  if (k > 1) {
+    // several attributes: the gradient with respect to them (on request) is a pass of its own over g_z1
+    HGNN_TRY(launch_segsum_vm(st, H, bf16, N, row_ptr, nullptr, w.gz1_vm, w.g_PQ, 2 * H, PT_SEGSUM_DST));
+    if (g_d2) HGNN_TRY(launch_gattr_vm(st, H, E, w.gz1_vm, W + o.W1 + 2 * HH, k, g_d2));
+  } else {
+    HGNN_TRY(launch_segsum_vm(st, H, bf16, N, row_ptr, nullptr, w.gz1_vm, w.g_PQ, 2 * H, PT_SEGSUM_DST,
+                              W + o.W1 + 2 * HH, g_d2));
+  }
   if (g_rvec) HGNN_TRY(launch_edge_grvec(st, E, dst, s.xe, g_v_out, alpha, g_rvec));
   HGNN_TRY(launch_segsum_vm(st, H, bf16, N, colT_ptr, permT, w.gz1_vm, w.g_PQ + H, 2 * H, PT_SEGSUM_SRC));  // g_Q
   HGNN_TRY(stream_after(sx, st, ss.ev[3]));
@@ -460,7 +485,7 @@ extern "C" int32_t hgnn_mp_layer_bwd(void* stream, int32_t N, int64_t E, int32_t
                                      const int32_t* permT, const float* h_in, const float* W, const void* saved,
                                      size_t saved_bytes, const float* g_h_out, const float* g_v_out,
                                      float* g_h_in, float* g_v_in, float* gW, void* ws, size_t ws_bytes) {
-  return mp_layer_bwd_impl(stream, N, E, H, dtype, alpha, row_ptr, dst, col, d2, rvec, colT_ptr, permT, h_in, W, saved,
+  return mp_layer_bwd_impl(stream, N, E, H, 1, dtype, alpha, row_ptr, dst, col, d2, rvec, colT_ptr, permT, h_in, W, saved,
                            saved_bytes, g_h_out, g_v_out, g_h_in, g_v_in, gW, ws, ws_bytes, nullptr, nullptr);
 }
 
@@ -477,14 +502,14 @@ static int32_t check_attr_args(int N, int64_t E, int H, int k, int dtype) {
                "layers with several edge attributes, or of a width other than 64, 128, 256, run with bf16 operands only");
   return HGNN_OK;
 }
-// one attribute (the squared edge length) at a width the fused kernels serve
-static bool attr_on_fused_kernels(int H, int k) { return k == 1 && valid_H(H); }
+// every width the fused kernels serve (several attributes: bf16 operands, which check_attr_args has made sure of)
+static bool attr_on_fused_kernels(int H, int k) { (void)k; return valid_H(H); }
 
 extern "C" int32_t hgnn_mp_layer_attr_workspace_bytes(int32_t N, int64_t E, int32_t H, int32_t k, int32_t dtype,
                                                       size_t* ws_bytes_host, size_t* saved_bytes_host) {
   HGNN_TRY(check_attr_args(N, E, H, k, dtype));
   HGNN_REQUIRE(ws_bytes_host && saved_bytes_host, HGNN_ERR_NULLPTR, "null size pointer");
-  if (attr_on_fused_kernels(H, k)) return hgnn_mp_layer_workspace_bytes(N, E, H, dtype, ws_bytes_host, saved_bytes_host);
+  if (attr_on_fused_kernels(H, k)) return layer_sizes(N, E, H, k, dtype, ws_bytes_host, saved_bytes_host);
   wide_layer_sizes(N, E, H, k, ws_bytes_host, saved_bytes_host);
   return HGNN_OK;
 }
@@ -497,7 +522,7 @@ extern "C" int32_t hgnn_mp_layer_attr_fwd(void* stream, int32_t N, int64_t E, in
   hipStream_t st = static_cast<hipStream_t>(stream);
   HGNN_TRY(check_attr_args(N, E, H, k, dtype));
   if (attr_on_fused_kernels(H, k))
-    return mp_layer_fwd_impl(stream, N, E, H, dtype, alpha, row_ptr, dst, col, attr, rvec, h_in, v_in, W, h_out, v_out,
+    return mp_layer_fwd_impl(stream, N, E, H, k, dtype, alpha, row_ptr, dst, col, attr, rvec, h_in, v_in, W, h_out, v_out,
                              saved, saved_bytes, ws, ws_bytes, true);
   if (N == 0) return HGNN_OK;
   HGNN_REQUIRE(row_ptr && h_in && v_in && W && h_out && v_out && ws && saved, HGNN_ERR_NULLPTR, "mp_layer_attr_fwd: null pointer");
@@ -525,7 +550,7 @@ extern "C" int32_t hgnn_mp_layer_attr_bwd(void* stream, int32_t N, int64_t E, in
   hipStream_t st = static_cast<hipStream_t>(stream);
   HGNN_TRY(check_attr_args(N, E, H, k, dtype));
   if (attr_on_fused_kernels(H, k))
-    return mp_layer_bwd_impl(stream, N, E, H, dtype, alpha, row_ptr, dst, col, attr, rvec, colT_ptr, permT, h_in, W,
+    return mp_layer_bwd_impl(stream, N, E, H, k, dtype, alpha, row_ptr, dst, col, attr, rvec, colT_ptr, permT, h_in, W,
                              saved, saved_bytes, g_h_out, g_v_out, g_h_in, g_v_in, gW, ws, ws_bytes, g_attr, g_rvec);
   HGNN_REQUIRE(gW && W && ws, HGNN_ERR_NULLPTR, "mp_layer_attr_bwd: null pointer");
   HGNN_REQUIRE(N == 0 || (row_ptr && colT_ptr && h_in && saved && g_h_out && g_v_out && g_h_in && g_v_in),

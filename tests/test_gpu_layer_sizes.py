@@ -209,7 +209,10 @@ def _run_layer_attr(N, E, H, k, seed, rc=5.0):
         assert e <= (tol["fwd"] if n in ("h", "v") else tol["grad"]), (n, e)
 
 
+# H = 64 / 128 / 256 run on the fused kernels (attribute term on the matrix cores): tile boundaries (64 edges), the
+# branch-free and the masked tile, every k residue of the four-slot staging, k = 16 (all slots) and k = 2
 @pytest.mark.parametrize("N,E,H,k", [(300, 5000, 866, 8), (200, 3001, 256, 16), (100, 1500, 64, 4), (64, 700, 333, 3),
-                                     (50, 0, 128, 5), (120, 2000, 300, 1)])
+                                     (50, 0, 128, 5), (120, 2000, 300, 1), (700, 40001, 256, 8), (300, 64, 256, 2),
+                                     (300, 8193, 128, 13), (90, 1000, 64, 16), (40, 63, 128, 7), (500, 20000, 256, 3)])
 def test_layer_with_edge_attributes(N, E, H, k):
     _run_layer_attr(N=N, E=E, H=H, k=k, seed=H + E + k)
