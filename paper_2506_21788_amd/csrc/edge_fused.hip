@@ -694,13 +694,15 @@ struct SegCols {
   static constexpr int NPASS = PAIRS ? NCB / 4 : NCB / 2;
   static constexpr int PER = PAIRS ? 2 : 1;
   __device__ static __forceinline__ void fetch(const void* __restrict__ X, size_t e, int c, int hp, int x, float* out) {
+    // streamed once: non-temporal, so that the lines do not displace what the neighbouring kernels keep in the L2
     if constexpr (PAIRS) {
-      const unsigned w = reinterpret_cast<const unsigned*>(X)[vm_index<NCB / 2>(e, 2 * c + hp, x)];
+      const unsigned w = __builtin_nontemporal_load(reinterpret_cast<const unsigned*>(X) + vm_index<NCB / 2>(e, 2 * c + hp, x));
       out[0] = __uint_as_float(w << 16);
       out[1] = __uint_as_float(w & 0xffff0000u);
     } else {
       const size_t idx = vm_index<NCB>(e, 2 * c + hp, x);
-      out[0] = BF16 ? bf_bits_to_f(reinterpret_cast<const unsigned short*>(X)[idx]) : reinterpret_cast<const float*>(X)[idx];
+      out[0] = BF16 ? bf_bits_to_f(__builtin_nontemporal_load(reinterpret_cast<const unsigned short*>(X) + idx))
+                    : __builtin_nontemporal_load(reinterpret_cast<const float*>(X) + idx);
     }
   }
   __device__ static __forceinline__ int column(int c, int hp, int x, int k) {
@@ -718,13 +720,13 @@ struct SegCols {
     const size_t first = (((size_t)(e >> 5) * NB) * 16 + 4 * (r >> 3) + (r & 3)) * 64 + ((r >> 2) & 1) * 32;
     const char* base = reinterpret_cast<const char*>(X) + first * ESZ;
     if constexpr (PAIRS) {
-      const unsigned w = *reinterpret_cast<const unsigned*>(base + loff);
+      const unsigned w = __builtin_nontemporal_load(reinterpret_cast<const unsigned*>(base + loff));
       out[0] = __uint_as_float(w << 16);
       out[1] = __uint_as_float(w & 0xffff0000u);
     } else if constexpr (BF16) {
-      out[0] = bf_bits_to_f(*reinterpret_cast<const unsigned short*>(base + loff));
+      out[0] = bf_bits_to_f(__builtin_nontemporal_load(reinterpret_cast<const unsigned short*>(base + loff)));
     } else {
-      out[0] = *reinterpret_cast<const float*>(base + loff);
+      out[0] = __builtin_nontemporal_load(reinterpret_cast<const float*>(base + loff));
     }
   }
 };
