@@ -220,55 +220,127 @@ __global__ void k_pool_bwd_any(int N, int G, int H, int mode, const int32_t* __r
 // ---------------------------------------------------------------------------------------------
 // routing plan
 // ---------------------------------------------------------------------------------------------
-// one block; thread s collects the graphs of source s in ascending order (stable by construction)
-__global__ void k_plan_graphs(int G, int S, const int32_t* __restrict__ graph_off, const int32_t* __restrict__ source_id,
-                              PlanView v) {
-  __shared__ int s_cnt[1024];
-  __shared__ int s_atoms[1024];
-  if (threadIdx.x == 0) v.status[0] = 0;
-  __syncthreads();
-  // validation + copy
-  for (int g = threadIdx.x; g < G; g += blockDim.x) {
-    const int s = source_id[g];
-    v.graph_src[g] = s;
-    if (s < 0 || s >= S) atomicOr(v.status, 1);
+// One workgroup. Counts per source (integer atomics: the sums do not depend on their order), an in-place scan over
+// the sources, then the stable placement: graphs are taken 1024 at a time, a thread ranks its graph among the
+// earlier graphs of the same source inside the chunk (all 1024 sources of the chunk sit in LDS) and adds the
+// per-source cursor that the chunks before it left behind.
+__global__ void __launch_bounds__(1024)
+k_plan_graphs(int G, int S, const int32_t* __restrict__ graph_off, const int32_t* __restrict__ source_id, PlanView v) {
+  __shared__ int sh_a[1024];
+  __shared__ int sh_b[1024];
+  const int tid = threadIdx.x;
+  if (tid == 0) v.status[0] = 0;
+  for (int s = tid; s <= S; s += 1024) {
+    v.grp_graph_ptr[s] = 0;
+    v.grp_atom_ptr[s] = 0;
   }
   __syncthreads();
+  // validation, copy, counts (entry s + 1 counts source s). Few sources: the counters live in LDS (many graphs hit
+  // few counters, which global atomics would serialise); many sources: global atomics.
+  const bool lds_counts = S <= 1024;
+  if (lds_counts) {
+    sh_a[tid] = 0;
+    sh_b[tid] = 0;
+    __syncthreads();
+  }
+  for (int g = tid; g < G; g += 1024) {
+    const int s = source_id[g];
+    v.graph_src[g] = s;
+    if (s < 0 || s >= S) {
+      atomicOr(v.status, 1);
+    } else if (lds_counts) {
+      atomicAdd(&sh_a[s], 1);
+      atomicAdd(&sh_b[s], graph_off[g + 1] - graph_off[g]);
+    } else {
+      atomicAdd(&v.grp_graph_ptr[s + 1], 1);
+      atomicAdd(&v.grp_atom_ptr[s + 1], graph_off[g + 1] - graph_off[g]);
+    }
+  }
+  if (lds_counts) {
+    __syncthreads();
+    if (tid < S) {
+      v.grp_graph_ptr[tid + 1] = sh_a[tid];
+      v.grp_atom_ptr[tid + 1] = sh_b[tid];
+    }
+  }
+  __threadfence_block();
+  __syncthreads();
   if (v.status[0]) return;
-  for (int s0 = 0; s0 < S; s0 += blockDim.x) {
-    const int s = s0 + threadIdx.x;
-    int cnt = 0, atoms = 0;
-    if (s < S) {
-      for (int g = 0; g < G; ++g)
-        if (source_id[g] == s) { ++cnt; atoms += graph_off[g + 1] - graph_off[g]; }
-    }
-    s_cnt[threadIdx.x] = cnt;
-    s_atoms[threadIdx.x] = atoms;
+  // inclusive scan over entries 0..S of both arrays, 1024 at a time with a carry
+  int carry_g = 0, carry_a = 0;
+  for (int s0 = 0; s0 <= S; s0 += 1024) {
+    const int s = s0 + tid;
+    int cg = s <= S ? v.grp_graph_ptr[s] : 0, ca = s <= S ? v.grp_atom_ptr[s] : 0;
+    sh_a[tid] = cg;
+    sh_b[tid] = ca;
     __syncthreads();
-    if (threadIdx.x == 0) {
-      int cg = s0 == 0 ? 0 : v.grp_graph_ptr[s0];
-      int ca = s0 == 0 ? 0 : v.grp_atom_ptr[s0];
-      for (int k = 0; k < (int)blockDim.x && s0 + k < S; ++k) {
-        v.grp_graph_ptr[s0 + k] = cg;
-        v.grp_atom_ptr[s0 + k] = ca;
-        cg += s_cnt[k];
-        ca += s_atoms[k];
-      }
-      const int last = (s0 + (int)blockDim.x < S) ? s0 + (int)blockDim.x : S;
-      v.grp_graph_ptr[last] = cg;
-      v.grp_atom_ptr[last] = ca;
+    for (int o = 1; o < 1024; o <<= 1) {
+      const int ag = tid >= o ? sh_a[tid - o] : 0, aa = tid >= o ? sh_b[tid - o] : 0;
+      __syncthreads();
+      sh_a[tid] += ag;
+      sh_b[tid] += aa;
+      __syncthreads();
     }
-    __syncthreads();
-    if (s < S) {
-      int kg = v.grp_graph_ptr[s], ka = v.grp_atom_ptr[s];
-      for (int g = 0; g < G; ++g)
-        if (source_id[g] == s) {
-          v.graph_perm[kg++] = g;
-          v.graph_dst_off[g] = ka;
-          ka += graph_off[g + 1] - graph_off[g];
-        }
+    if (s <= S) {
+      v.grp_graph_ptr[s] = carry_g + sh_a[tid];
+      v.grp_atom_ptr[s] = carry_a + sh_b[tid];
     }
+    carry_g += sh_a[1023];
+    carry_a += sh_b[1023];
     __syncthreads();
+  }
+  __threadfence_block();
+  __syncthreads();
+  // stable placement by one wavefront, 64 graphs at a time: a lane ranks its graph among the earlier lanes of the
+  // same source (lane values are read one by one), adds the cursor that the groups before left for that source, and
+  // the last lane of every source moves the cursor on. The cursors live in LDS when they fit.
+  int* cur_g = lds_counts ? sh_a : v.cur_graph;
+  int* cur_a = lds_counts ? sh_b : v.cur_atom;
+  for (int s = tid; s < S; s += 1024) {
+    cur_g[s] = v.grp_graph_ptr[s];
+    cur_a[s] = v.grp_atom_ptr[s];
+  }
+  __threadfence_block();
+  __syncthreads();
+  if (tid >= 64) return;
+  // the next group's source and atom count are asked for while this group is placed
+  int s_nx = tid < G ? source_id[tid] : -1;
+  int na_nx = tid < G ? graph_off[tid + 1] - graph_off[tid] : 0;
+  for (int g0 = 0; g0 < G; g0 += 64) {
+    const int g = g0 + tid;
+    const bool on = g < G;
+    const int s = s_nx, na = na_nx;
+    {
+      const int gn = g + 64;
+      s_nx = gn < G ? source_id[gn] : -1;
+      na_nx = gn < G ? graph_off[gn + 1] - graph_off[gn] : 0;
+    }
+    int before = 0, atoms_before = 0;
+    bool last = true;
+    const int n = G - g0 < 64 ? G - g0 : 64;
+    for (int t = 0; t < n; ++t) {
+      const int st = __builtin_amdgcn_readlane(s, t), nt = __builtin_amdgcn_readlane(na, t);
+      const bool same = st == s;
+      if (same && t < tid) { ++before; atoms_before += nt; }
+      if (same && t > tid) last = false;
+    }
+    int bg = 0, ba = 0;
+    if (on) {
+      bg = cur_g[s];
+      ba = cur_a[s];
+      v.graph_perm[bg + before] = g;
+      v.graph_dst_off[g] = ba + atoms_before;
+    }
+    // every lane has read the cursors before any of them moves on (LDS accesses of one wavefront complete in
+    // order; cursors in global memory need the fence)
+    if (!lds_counts) __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
+    __builtin_amdgcn_wave_barrier();
+    if (on && last) {
+      cur_g[s] = bg + before + 1;
+      cur_a[s] = ba + atoms_before + na;
+    }
+    if (!lds_counts) __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
+    __builtin_amdgcn_wave_barrier();
   }
 }
 

@@ -7,6 +7,7 @@ namespace hgnn {
 
 struct PlanView {
   int32_t *grp_graph_ptr, *graph_perm, *grp_atom_ptr, *atom_perm, *atom_graph, *graph_src, *graph_dst_off, *status;
+  int32_t *cur_graph, *cur_atom;   // [S] each: running cursors of the stable placement
   int64_t ints;
 };
 
@@ -23,6 +24,8 @@ static PlanView plan_view(T* plan, int N, int G, int S) {
   v.graph_src = p + o; o += G;
   v.graph_dst_off = p + o; o += G;
   v.status = p + o; o += 4;
+  v.cur_graph = p + o; o += S;
+  v.cur_atom = p + o; o += S;
   v.ints = o;
   return v;
 }
