@@ -290,9 +290,9 @@ def main():
     ap.add_argument("--hip-graph", action="store_true",
                     help="also time forward + backward replayed as one HIP graph (graph prebuilt)")
     ap.add_argument("--rbf", type=int, default=0, metavar="K",
-                    help="K radial-basis edge attributes in place of d2 (2..16; every layer then runs on the fragment path)")
+                    help="K radial-basis edge attributes in place of d2 (2..16)")
     ap.add_argument("--pos-grad", action="store_true",
-                    help="the reverse pass also gives the gradient with respect to positions (fragment path, bf16)")
+                    help="the reverse pass also gives the gradient with respect to positions")
     ap.add_argument("--move", action="store_true",
                     help="the atoms move between layers (edge geometry recomputed per layer; implies --pos-grad)")
     ap.add_argument("--calib-copy", action="store_true", help="only run a 1 GiB copy kernel (counter calibration)")
