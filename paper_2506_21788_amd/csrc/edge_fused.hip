@@ -1626,198 +1626,188 @@ k_wgrad_frag(int64_t nblk32, const void* __restrict__ a1_pk, const void* __restr
 
 
 // The same weight gradient with a1 = silu(z1) recomputed from the projected node features instead of read back
-// (bf16 pairs, H = 256 only): the forward pass then never stores a1, and this kernel trades its idle vector units
-// for half of its memory traffic. Per 16-edge chunk a wavefront gathers P[dst] and Q[col] for its own two column
-// blocks (one pair word per row), forms the two A operands in registers, and multiplies them with all eight g_z2
-// operands of the chunk. Those are loaded once per workgroup (two blocks per wavefront) and shared through a ring
-// of LDS stages. Everything is software-pipelined with fixed register rings: g_z2 four chunks ahead, gathers three
-// chunks ahead, the edge indices they need one chunk before that; one barrier per chunk publishes the next stage.
+// (bf16 pairs, H = 256 only): the forward pass then never stores a1, and this kernel trades vector work for half of
+// its memory traffic. One workgroup of eight wavefronts per compute unit holds the whole H x H accumulator (two row
+// blocks x four column blocks per wavefront), so two wavefronts share a SIMD and one's sigmoids overlap the other's
+// matrix products. Per 16-edge chunk every wavefront is a producer first: for four consecutive edges (the same for
+// all its lanes, so their indices sit in scalar registers and a gather is one 256-byte piece of a row) it gathers
+// 64 pair words of P[dst] and Q[col], forms silu(z1) for the four column blocks those words cover and writes its
+// share of four A operands into an LDS stage; it also loads one of the eight g_z2 operands of the chunk for the
+// workgroup. Everything is software-pipelined with fixed register rings. Loads complete in the order they were
+// issued, so what counts is the shortest distance between any load and its first use: every load here is used at
+// least three chunks after it was issued (edge indices eight chunks ahead, used for the gathers four chunks ahead;
+// g_z2 eight chunks ahead). One barrier per chunk publishes the next stage (two stages: chunk c is multiplied while
+// chunk c + 1 is written).
 struct WgradRcArgs {
-  int64_t blk0;      // first 32-edge block of this launch
-  int64_t nblk32;    // number of blocks of this launch
+  int64_t nblk32;    // number of 32-edge blocks, the last one possibly ragged
   int E;
   const int32_t *dst, *col;
   const float* d2;
   const void* PQ;
   const float* w1d;
-  const void* gz2_pk;
+  const void* gz2_pk;   // rows past the last edge of the last block hold zeros
   float* partial;
 };
 
-// CHECK: the blocks of this launch may reach past the last edge, and a workgroup's chunk count need not be a
-// multiple of four (only the launch for the left-over blocks)
-template <int H, bool CHECK>
-__global__ void __launch_bounds__(256) k_wgrad_frag_rc(WgradRcArgs p) {
+template <int H>
+__global__ void __launch_bounds__(512) k_wgrad_frag_rc(WgradRcArgs p) {
   constexpr int NCB = H / 32;
-  constexpr int NBA = 2;         // A blocks per wavefront, recomputed by this wavefront only
-  constexpr int NBB = NCB;       // every wavefront multiplies them with all column blocks of g_z2
-  constexpr int NBL = NCB / 4;   // g_z2 blocks each wavefront loads for the workgroup
-  constexpr int NSTAGE = 4;
-  static_assert(H == 256, "pair storage");
+  constexpr int STAGE = NCB * 1024;   // bytes of the eight operands of one kind for one chunk
+  static_assert(H == 256, "pair storage, eight wavefronts");
   using PQP = PQPitch<H, true>;
-  __shared__ __align__(16) unsigned char stage[NSTAGE * NCB * 1024];
+  __shared__ __align__(16) unsigned char stage_a[4 * STAGE];
+  __shared__ __align__(16) unsigned char stage_b[4 * STAGE];
   const int lane = threadIdx.x & 63;
-  const int wa = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-  const int g = lane >> 5, x = lane & 31;
-  f32x16_t acc[NBA][NBB];
+  const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+  const int x = lane & 31;
+  // as a producer: words wcc * 64 + lane of a row, i.e. pair group pg, column blocks 2 pg (low halves) and 2 pg + 1;
+  // edges 4 q .. 4 q + 3 of the chunk, which are elements 4 (q >> 1) .. + 3 of operand lane group q & 1
+  const int wcc = w >> 2, q = w & 3;
+  const int pg = 2 * wcc + (lane >> 5);
+  // as a consumer: A blocks 2 ra, 2 ra + 1; g_z2 blocks 4 cb .. 4 cb + 3
+  const int ra = w >> 1, cb = w & 1;
+  f32x16_t acc[2][4];
 #pragma unroll
-  for (int i = 0; i < NBA; ++i)
+  for (int i = 0; i < 2; ++i)
 #pragma unroll
-    for (int j = 0; j < NBB; ++j)
+    for (int j = 0; j < 4; ++j)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-  float w1d[NBA];
-#pragma unroll
-  for (int i = 0; i < NBA; ++i) w1d[i] = p.w1d[(wa * NBA + i) * 32 + x];
-  const int G = gridDim.x;
-  const int nblk = (int)p.nblk32, blk0 = (int)p.blk0;
-  const int nmine = nblk > (int)blockIdx.x ? (nblk - (int)blockIdx.x + G - 1) / G : 0;
-  const int nchunk = nmine * 2;   // two 16-edge chunks per 32-edge block; a multiple of 4 unless CHECK
+  const float w1lo = p.w1d[pg * 64 + x], w1hi = p.w1d[pg * 64 + 32 + x];
+  const int G = gridDim.x, bid = blockIdx.x;
+  const int nblk = (int)p.nblk32;
   const int E = p.E;
-  const unsigned colb = (unsigned)(wa * 32 + x) * 4u;   // this lane's pair word inside a row
-  typedef int i32x4_t __attribute__((ext_vector_type(4)));
-  // Which blocks are this workgroup's: the main launch (every workgroup has the same count) gives each XCD
-  // (workgroups are dealt to the 8 XCDs round-robin) a contiguous eighth of the blocks, dealt round-robin inside
-  // the XCD, so that the node rows an XCD gathers stay in its own L2; otherwise plain round-robin.
-  const bool by_xcd = !CHECK && (G & 7) == 0;
-  const int bstride = by_xcd ? (G >> 3) : G;
-  const int bfirst = blk0 + (by_xcd ? ((int)blockIdx.x & 7) * (nmine * bstride) + ((int)blockIdx.x >> 3) : (int)blockIdx.x);
+  // Which blocks are this workgroup's: with a grid that is a multiple of eight every XCD (workgroups are dealt to
+  // the 8 XCDs round-robin) takes a contiguous eighth of the blocks, dealt round-robin inside the XCD, so that the
+  // node rows an XCD gathers stay in its own L2; otherwise plain round-robin.
+  int bfirst, bstride, nmine;
+  if ((G & 7) == 0) {
+    const int xcd = bid & 7, r = bid >> 3;
+    bstride = G >> 3;
+    const int lo = (int)((int64_t)nblk * xcd / 8), hi = (int)((int64_t)nblk * (xcd + 1) / 8);
+    nmine = hi - lo > r ? (hi - lo - r + bstride - 1) / bstride : 0;
+    bfirst = lo + r;
+  } else {
+    bstride = G;
+    nmine = nblk > bid ? (nblk - bid + G - 1) / G : 0;
+    bfirst = bid;
+  }
+  const int nchunk = nmine * 2;   // two 16-edge chunks per 32-edge block
+  const unsigned colb = (unsigned)(wcc * 64 + lane) * 4u;   // this lane's pair word inside a row
+  // lanes 0..3 fetch dst, 4..7 col, 8..11 d2 of the wavefront's four edges
+  const int32_t* const idx_arr = lane < 4 ? p.dst : (lane < 8 ? p.col : reinterpret_cast<const int32_t*>(p.d2));
+  unsigned char* const a_out = stage_a + (2 * pg) * 1024 + ((q & 1) * 32 + x) * 16 + 8 * (q >> 1);
 
-  // chunk c (clamped to this workgroup's last chunk): its 32-edge block, and the first edge of this lane's two
-  // groups of four consecutive edges
-#define HGNN_RC_CC(c) ((c) < nchunk ? (c) : nchunk - 1)
-#define HGNN_RC_BLK(cc) (bfirst + ((cc) >> 1) * bstride)
-#define HGNN_RC_E0(cc) (HGNN_RC_BLK(cc) * 32 + ((cc) & 1) * 16 + 4 * g)
-  // indices of the 8 edges (CHECK: zeros past the last edge; row 0 is always a valid row)
-#define HGNN_RC_IDX(c, di, ci)                                                                         \
-  {                                                                                                    \
-    const int cc_ = HGNN_RC_CC(c);                                                                     \
-    const int e0_ = HGNN_RC_E0(cc_);                                                                   \
-    _Pragma("unroll") for (int h = 0; h < 2; ++h) {                                                    \
-      const int e_ = e0_ + 8 * h;                                                                      \
-      i32x4_t a_ = {0, 0, 0, 0}, b_ = {0, 0, 0, 0};                                                    \
-      if (!CHECK || e_ + 3 < E) {                                                                      \
-        a_ = ldg_at<i32x4_t>(p.dst, (unsigned)e_ * 4u);                                                \
-        b_ = ldg_at<i32x4_t>(p.col, (unsigned)e_ * 4u);                                                \
-      } else {                                                                                         \
-        if (e_ < E) { a_[0] = p.dst[e_]; b_[0] = p.col[e_]; }                                          \
-        if (e_ + 1 < E) { a_[1] = p.dst[e_ + 1]; b_[1] = p.col[e_ + 1]; }                              \
-        if (e_ + 2 < E) { a_[2] = p.dst[e_ + 2]; b_[2] = p.col[e_ + 2]; }                              \
-      }                                                                                                \
-      _Pragma("unroll") for (int k = 0; k < 4; ++k) { di[4 * h + k] = a_[k]; ci[4 * h + k] = b_[k]; }  \
-    }                                                                                                  \
-  }
-  // gathers of chunk c: pair words of P and Q, and d2
-#define HGNN_RC_GATHER(c, di, ci, wp, wq, dd)                                                          \
-  {                                                                                                    \
-    const int cc_ = HGNN_RC_CC(c);                                                                     \
-    const int e0_ = HGNN_RC_E0(cc_);                                                                   \
-    _Pragma("unroll") for (int h = 0; h < 2; ++h) {                                                    \
-      const int e_ = e0_ + 8 * h;                                                                      \
-      f32x4_t d_ = {0.f, 0.f, 0.f, 0.f};                                                               \
-      if (!CHECK || e_ + 3 < E) d_ = ldg_at<f32x4_t>(p.d2, (unsigned)e_ * 4u);                         \
-      else {                                                                                           \
-        if (e_ < E) d_[0] = p.d2[e_];                                                                  \
-        if (e_ + 1 < E) d_[1] = p.d2[e_ + 1];                                                          \
-        if (e_ + 2 < E) d_[2] = p.d2[e_ + 2];                                                          \
-      }                                                                                                \
-      _Pragma("unroll") for (int k = 0; k < 4; ++k) dd[4 * h + k] = d_[k];                             \
-    }                                                                                                  \
-    _Pragma("unroll") for (int u = 0; u < 8; ++u) {                                                    \
-      wp[u] = ldg_u32(p.PQ, (unsigned)di[u] * PQP::ROW + colb);                                        \
-      wq[u] = ldg_u32(p.PQ, (unsigned)ci[u] * PQP::ROW + colb + PQP::QOFF);                            \
-    }                                                                                                  \
-  }
-  // this wavefront's share of the g_z2 operands of chunk c: memory -> registers, registers -> LDS stage
-#define HGNN_RC_LOADB(c, b)                                                                            \
-  {                                                                                                    \
-    const int cc_ = HGNN_RC_CC(c);                                                                     \
-    const size_t eb_ = (size_t)HGNN_RC_BLK(cc_);                                                       \
-    _Pragma("unroll") for (int j = 0; j < NBL; ++j)                                                    \
-      b[j] = ldg_nt<bf16x8_t>(uoff(p.gz2_pk, (((eb_ * NCB + wa * NBL + j) * 2 + (cc_ & 1)) * 1024)), lane * 16u); \
-  }
-#define HGNN_RC_STAGEB(st, b)                                                                          \
-  _Pragma("unroll") for (int j = 0; j < NBL; ++j)                                                      \
-    *reinterpret_cast<bf16x8_t*>(stage + ((st) * NCB + wa * NBL + j) * 1024 + lane * 16) = b[j];
-  // A operands from the gathered words, all g_z2 operands of the chunk from its LDS stage, then the products
-  // (CHECK: A is zeroed for chunks past the end)
-#define HGNN_RC_MMA(c, st, wp, wq, dd)                                                                 \
-  {                                                                                                    \
-    const bool ok_ = !CHECK || (c) < nchunk;                                                           \
-    bf16x8_t b_[NBB];                                                                                  \
-    _Pragma("unroll") for (int j = 0; j < NBB; ++j)                                                    \
-      b_[j] = *reinterpret_cast<const bf16x8_t*>(stage + ((st) * NCB + j) * 1024 + lane * 16);         \
-    _Pragma("unroll") for (int i = 0; i < NBA; ++i) {                                                  \
-      float v_[8];                                                                                     \
-      _Pragma("unroll") for (int u = 0; u < 8; ++u) {                                                  \
-        const unsigned a_ = wp[u], q_ = wq[u];                                                         \
-        const float z_ = ((i & 1) ? __uint_as_float(a_ & 0xffff0000u) + __uint_as_float(q_ & 0xffff0000u) \
-                                  : __uint_as_float(a_ << 16) + __uint_as_float(q_ << 16)) + dd[u] * w1d[i]; \
-        v_[u] = ok_ ? silu_f(z_) : 0.f;                                                                \
-      }                                                                                                \
-      typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));                                    \
-      const u32x4_t w_ = {pack_bf16x2(v_[0], v_[1]), pack_bf16x2(v_[2], v_[3]), pack_bf16x2(v_[4], v_[5]), \
-                          pack_bf16x2(v_[6], v_[7])};                                                  \
-      const bf16x8_t az_ = __builtin_bit_cast(bf16x8_t, w_);                                           \
-      _Pragma("unroll") for (int j = 0; j < NBB; ++j)                                                  \
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(az_, b_[j], acc[i][j], 0, 0, 0);         \
-    }                                                                                                  \
-  }
-  // one pipeline step for chunk c with the ring slots named explicitly (k = c mod 4):
-  //   stage chunk c+1's g_z2, ask for chunk c+4's, gather chunk c+3, ask for the indices of chunk c+4,
-  //   barrier, multiply chunk c
-#define HGNN_RC_STEP(c, k, bN, bL, diG, ciG, diL, ciL, wpG, wqG, ddG, wpM, wqM, ddM)                   \
-  HGNN_RC_STAGEB(((k) + 1) & 3, bN)                                                                    \
-  HGNN_RC_LOADB((c) + 4, bL)                                                                           \
-  HGNN_RC_GATHER((c) + 3, diG, ciG, wpG, wqG, ddG)                                                     \
-  HGNN_RC_IDX((c) + 4, diL, ciL)                                                                       \
-  __syncthreads();                                                                                     \
-  HGNN_RC_MMA(c, k, wpM, wqM, ddM)
+  // chunk c, clamped to this workgroup's last chunk: its block, and which half of it
+  auto chunk_blk = [&](int c) { const int cc = c < nchunk ? c : nchunk - 1; return bfirst + (cc >> 1) * bstride; };
+  auto chunk_half = [&](int c) { const int cc = c < nchunk ? c : nchunk - 1; return cc & 1; };
+  // indices and d2 of the wavefront's four edges of chunk c, one value per lane (zeros past the last edge: row 0 is
+  // always a valid row, and g_z2 is zero there)
+  auto load_iv = [&](int c, int& iv) {
+    const int e = chunk_blk(c) * 32 + chunk_half(c) * 16 + 4 * q + (lane & 3);
+    iv = 0;
+    if (lane < 12 && e < E) iv = idx_arr[e];
+  };
+  auto gather = [&](const int iv, unsigned (&wp)[4], unsigned (&wq)[4]) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const unsigned rd = (unsigned)__builtin_amdgcn_readlane(iv, u), rc = (unsigned)__builtin_amdgcn_readlane(iv, 4 + u);
+      wp[u] = ldg_u32(uoff(p.PQ, rd * PQP::ROW), colb);
+      wq[u] = ldg_u32(uoff(p.PQ, rc * PQP::ROW + PQP::QOFF), colb);
+    }
+  };
+  // this wavefront's g_z2 operand of chunk c (column block w): memory -> registers, registers -> LDS stage
+  auto load_b = [&](int c, bf16x8_t& b) {
+    b = ldg_nt<bf16x8_t>(uoff(p.gz2_pk, (((size_t)chunk_blk(c) * NCB + w) * 2 + chunk_half(c)) * 1024), lane * 16u);
+  };
+  auto stage_b_put = [&](int st, const bf16x8_t& b) {
+    *reinterpret_cast<bf16x8_t*>(stage_b + st * STAGE + w * 1024 + lane * 16) = b;
+  };
+  // this wavefront's share of four A operands of chunk c (zeros for chunks past the workgroup's last one)
+  auto stage_a_put = [&](int c, int st, const unsigned (&wp)[4], const unsigned (&wq)[4], const int iv) {
+    float vl[4], vh[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const unsigned a = wp[u], b = wq[u];
+      const float d = __int_as_float(__builtin_amdgcn_readlane(iv, 8 + u));
+      vl[u] = silu_f((__uint_as_float(a << 16) + __uint_as_float(b << 16)) + d * w1lo);
+      vh[u] = silu_f((__uint_as_float(a & 0xffff0000u) + __uint_as_float(b & 0xffff0000u)) + d * w1hi);
+    }
+    // no branch here: the sigmoids are meant to be scheduled between the matrix products of the same step
+    const unsigned keep = c < nchunk ? 0xffffffffu : 0u;   // uniform over the workgroup
+    const uint2 lo = make_uint2(pack_bf16x2(vl[0], vl[1]) & keep, pack_bf16x2(vl[2], vl[3]) & keep);
+    const uint2 hi = make_uint2(pack_bf16x2(vh[0], vh[1]) & keep, pack_bf16x2(vh[2], vh[3]) & keep);
+    *reinterpret_cast<uint2*>(a_out + st * STAGE) = lo;
+    *reinterpret_cast<uint2*>(a_out + st * STAGE + 1024) = hi;
+  };
+  auto mma_fetch = [&](int st, bf16x8_t (&a)[2], bf16x8_t (&b)[4]) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+      a[i] = *reinterpret_cast<const bf16x8_t*>(stage_a + st * STAGE + (2 * ra + i) * 1024 + lane * 16);
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      b[j] = *reinterpret_cast<const bf16x8_t*>(stage_b + st * STAGE + (4 * cb + j) * 1024 + lane * 16);
+  };
+  auto mma = [&](const bf16x8_t (&a)[2], const bf16x8_t (&b)[4]) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+  };
+
   if (nchunk > 0) {   // uniform over the workgroup
-    int di0[8], ci0[8], di1[8], ci1[8];                       // index ring: slot = chunk mod 2
-    unsigned wp0[8], wq0[8], wp1[8], wq1[8], wp2[8], wq2[8], wp3[8], wq3[8];   // gather ring: slot = chunk mod 4
-    float dd0[8], dd1[8], dd2[8], dd3[8];
-    bf16x8_t b0[NBL], b1[NBL], b2[NBL], b3[NBL];              // g_z2 load ring: slot = chunk mod 4
-    // prologue: g_z2 of chunks 0..3, gathers of chunks 0..2, indices of chunk 3, chunk 0 staged
-    HGNN_RC_LOADB(0, b0)
-    HGNN_RC_LOADB(1, b1)
-    HGNN_RC_LOADB(2, b2)
-    HGNN_RC_LOADB(3, b3)
-    HGNN_RC_IDX(0, di0, ci0)
-    HGNN_RC_GATHER(0, di0, ci0, wp0, wq0, dd0)
-    HGNN_RC_IDX(1, di1, ci1)
-    HGNN_RC_GATHER(1, di1, ci1, wp1, wq1, dd1)
-    HGNN_RC_IDX(2, di0, ci0)
-    HGNN_RC_GATHER(2, di0, ci0, wp2, wq2, dd2)
-    HGNN_RC_IDX(3, di1, ci1)
-    HGNN_RC_STAGEB(0, b0)
+    int iv[8];                            // index ring: slot = chunk mod 8
+    unsigned wp[4][4], wq[4][4];          // gather ring: slot = chunk mod 4
+    bf16x8_t bb[8];                       // g_z2 load ring: slot = chunk mod 8
+    // prologue: g_z2 and indices of chunks 0..7, gathers of chunks 0..3, chunks 0 and 1 staged
+#pragma unroll
+    for (int k = 0; k < 8; ++k) load_b(k, bb[k]);
+#pragma unroll
+    for (int k = 0; k < 8; ++k) load_iv(k, iv[k]);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) gather(iv[k], wp[k], wq[k]);
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+      stage_b_put(k, bb[k]);
+      stage_a_put(k, k, wp[k], wq[k], iv[k]);
+    }
     __syncthreads();
-    for (int c = 0; c < nchunk; c += 4) {
-      //           chunk  k  stage-from load-into  gather idx      next idx     gather-into        multiply-from
-      HGNN_RC_STEP(c,     0, b1,        b0,        di1, ci1,       di0, ci0,    wp3, wq3, dd3,     wp0, wq0, dd0)
-      HGNN_RC_STEP(c + 1, 1, b2,        b1,        di0, ci0,       di1, ci1,    wp0, wq0, dd0,     wp1, wq1, dd1)
-      HGNN_RC_STEP(c + 2, 2, b3,        b2,        di1, ci1,       di0, ci0,    wp1, wq1, dd1,     wp2, wq2, dd2)
-      HGNN_RC_STEP(c + 3, 3, b0,        b3,        di0, ci0,       di1, ci1,    wp2, wq2, dd2,     wp3, wq3, dd3)
+    for (int c = 0; c < nchunk; c += 8) {
+      // step for chunk j = c + k: fetch the operands of chunk j from their stage, ask for the g_z2 of chunk j + 8,
+      // gather chunk j + 4, ask for the indices of chunk j + 8, multiply chunk j while chunk j + 2 is formed and
+      // staged; a barrier after every second step (four stages)
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        bf16x8_t oa[2], ob[4];
+        mma_fetch(k & 3, oa, ob);
+        load_b(c + k + 8, bb[k]);
+        gather(iv[(k + 4) & 7], wp[k & 3], wq[k & 3]);
+        load_iv(c + k + 8, iv[k]);
+        mma(oa, ob);
+        stage_b_put((k + 2) & 3, bb[(k + 2) & 7]);
+        stage_a_put(c + k + 2, (k + 2) & 3, wp[(k + 2) & 3], wq[(k + 2) & 3], iv[(k + 2) & 7]);
+        // one matrix product, then a share of the vector work, eight times: a wavefront's products then run behind
+        // its own sigmoids instead of blocking both wavefronts of the SIMD at the start of every step
+        __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);
+        __builtin_amdgcn_sched_group_barrier(0x002, 20, 0);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x002, 10, 0);
+        }
+        if (k & 1) __syncthreads();
+      }
     }
   }
-#undef HGNN_RC_CC
-#undef HGNN_RC_BLK
-#undef HGNN_RC_E0
-#undef HGNN_RC_IDX
-#undef HGNN_RC_GATHER
-#undef HGNN_RC_LOADB
-#undef HGNN_RC_STAGEB
-#undef HGNN_RC_MMA
-#undef HGNN_RC_STEP
   float* out = p.partial + (size_t)blockIdx.x * H * H;
 #pragma unroll
-  for (int i = 0; i < NBA; ++i)
+  for (int i = 0; i < 2; ++i)
 #pragma unroll
-    for (int j = 0; j < NBB; ++j)
+    for (int j = 0; j < 4; ++j)
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        const int k1 = (wa * NBA + i) * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-        const int k2 = j * 32 + (lane & 31);
+        const int k1 = (2 * ra + i) * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+        const int k2 = (4 * cb + j) * 32 + (lane & 31);
         out[k1 * H + k2] = acc[i][j][v];
       }
 }
@@ -1864,37 +1854,24 @@ int32_t launch_wgrad_frag_recompute(hipStream_t st, int H, int64_t E, const int3
   HGNN_REQUIRE(H == 256, HGNN_ERR_BAD_SHAPE, "the recomputing weight-gradient kernel needs bf16 pairs (H = 256)");
   HGNN_REQUIRE(E >= 0 && E <= EDGE_MAX_E, HGNN_ERR_BAD_SHAPE, "edge kernels index edges with 32 bits (E = %lld)",
                (long long)E);
-  // The branch-free kernel takes the same even number of whole 32-edge blocks per workgroup; the blocks left over
-  // (fewer than two per workgroup, and the ragged last one) go to a second launch of the checking variant, two
-  // blocks per workgroup. Every workgroup of both launches leaves one partial.
-  const int64_t nfull = E / 32, ntail = (E % 32) ? 1 : 0;
+  // One workgroup per compute unit, each leaving one partial; fewer when there are fewer than two blocks for each
+  // (a multiple of eight where possible, so that the blocks are dealt by XCD). E == 0: one workgroup writes zeros.
+  const int64_t nblk32 = (E + 31) / 32;
   int64_t grid = num_cus();
-  if (grid > WGRAD_FRAG_MAX_GRID / 2) grid = WGRAD_FRAG_MAX_GRID / 2;
-  const int64_t per = (nfull / grid) & ~(int64_t)1;
-  const int64_t nmain = per * grid;
-  const int64_t nrest = nfull - nmain + ntail;
-  int64_t grid2 = (nrest + 1) / 2;
-  if (per == 0) grid = 0;
-  if (grid + grid2 == 0) grid2 = 1;   // E == 0: one workgroup writes a zero partial
+  if (grid > WGRAD_FRAG_MAX_GRID) grid = WGRAD_FRAG_MAX_GRID;
+  if (grid > (nblk32 + 1) / 2) grid = (nblk32 + 1) / 2;
+  if (grid >= 8) grid &= ~(int64_t)7;
+  if (grid < 1) grid = 1;
   WgradRcArgs a;
-  a.E = (int)E; a.dst = dst; a.col = col; a.d2 = d2; a.PQ = PQ; a.w1d = w1d;
-  a.gz2_pk = gz2_pk;
+  a.nblk32 = nblk32; a.E = (int)E; a.dst = dst; a.col = col; a.d2 = d2; a.PQ = PQ; a.w1d = w1d;
+  a.gz2_pk = gz2_pk; a.partial = partial;
   {
     ProfScope ps(PT_WGRAD_EDGE, st);
-    if (grid > 0) {
-      a.blk0 = 0; a.nblk32 = nmain; a.partial = partial;
-      k_wgrad_frag_rc<256, false><<<dim3((unsigned)grid), 256, 0, st>>>(a);
-      HGNN_LAUNCH_CHECK("k_wgrad_frag_rc");
-    }
-    if (grid2 > 0) {
-      a.blk0 = nmain; a.nblk32 = nrest; a.partial = partial + (size_t)grid * H * H;
-      k_wgrad_frag_rc<256, true><<<dim3((unsigned)grid2), 256, 0, st>>>(a);
-      HGNN_LAUNCH_CHECK("k_wgrad_frag_rc");
-    }
+    k_wgrad_frag_rc<256><<<dim3((unsigned)grid), 512, 0, st>>>(a);
+    HGNN_LAUNCH_CHECK("k_wgrad_frag_rc");
   }
-  const int nparts = (int)(grid + grid2);
   float* dest[4] = {gW2, nullptr, nullptr, nullptr};
-  return launch_reduce_partials(st, partial, nparts, 1, (long)H * H, dest, 1, 0);
+  return launch_reduce_partials(st, partial, (int)grid, 1, (long)H * H, dest, 1, 0);
 }
 
 }  // namespace hgnn
