@@ -48,6 +48,7 @@ struct GemmArgs {
   int mul_is_z = 0;
   const float* add1 = nullptr;
   int ldadd1 = 0;
+  int add1_cb_mask = 3;      // bit cb set: add1 applies to that column block
   const float* add2 = nullptr;
   int ldadd2 = 0;
   float* C = nullptr;
@@ -63,6 +64,10 @@ struct GemmArgs {
   int tag = PT_GEMM_NODE;  // timing class
 };
 int32_t launch_gemm(hipStream_t st, int H, bool bf16, const GemmArgs& a);
+// Two products in a row per row tile, the second one reading the first one's finished tile (through silu when
+// keep_silu is set) from LDS instead of its own A; with first == nullptr the second one alone, its A tile (one k
+// chunk) staged once for all of its column blocks. One launch; no groups, no row indirection.
+int32_t launch_gemm_chain(hipStream_t st, int H, bool bf16, const GemmArgs* first, const GemmArgs& second, int keep_silu);
 
 // ---- transposed GEMM (sum over rows of outer products), split-K ------------------------------
 // block (ia, ib): out[k1][k2] = sum_r f(A[ia][r][k1]) * B[ib][r][k2]

@@ -107,32 +107,13 @@ __device__ __forceinline__ bool tile_of_group(const int32_t* grp_ptr, int S, int
   return false;
 }
 
+// The three parts of a row-tile product. They share the workgroup's LDS: the A tile of one k chunk, then (after a
+// barrier) the accumulators on their way to row-major stores.
 template <int H, bool BF16, int TM>
-__global__ void __launch_bounds__(256, TM <= 32 ? 4 : 2) k_gemm(GemmArgs p) {
+__device__ __forceinline__ void gemm_stage_a(const GemmArgs& p, int kc, int rbeg, int rend, unsigned char* smem) {
   using C = GemmCfg<H, BF16, TM>;
-  extern __shared__ __align__(16) unsigned char smem[];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wr = wave / C::WC, wc = wave % C::WC;
-  const int cb = blockIdx.y;
-  int grp = 0, rbeg, rend;
-  if (p.grp_ptr) {
-    if (!tile_of_group(p.grp_ptr, p.S, C::TM, blockIdx.x, grp, rbeg, rend)) return;
-  } else {
-    rbeg = blockIdx.x * C::TM;
-    rend = p.M;
-    if (rbeg >= rend) return;
-  }
-
-  f32x16_t acc[C::RB][C::CB];
-#pragma unroll
-  for (int i = 0; i < C::RB; ++i)
-#pragma unroll
-    for (int j = 0; j < C::CB; ++j)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-
-  for (int kc = 0; kc < p.nkc; ++kc) {
-    if (kc) __syncthreads();
+  const int tid = threadIdx.x;
+  {
     // ---- stage the A tile (rows rbeg.., all H columns of chunk kc) into LDS
     const float* __restrict__ A = p.A[kc];
     const int lda = p.lda[kc];
@@ -171,7 +152,16 @@ __global__ void __launch_bounds__(256, TM <= 32 ? 4 : 2) k_gemm(GemmArgs p) {
         }
       }
     }
-    __syncthreads();
+  }
+}
+
+template <int H, bool BF16, int TM>
+__device__ __forceinline__ void gemm_multiply(const GemmArgs& p, int kc, int cb, int grp, const unsigned char* smem,
+                                              f32x16_t (&acc)[GemmCfg<H, BF16, TM>::RB][GemmCfg<H, BF16, TM>::CB]) {
+  using C = GemmCfg<H, BF16, TM>;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wr = wave / C::WC, wc = wave % C::WC;
+  {
     // ---- multiply. All workgroups run this loop at about the same time over the same packed block: each starts at
     // a different k step so that they do not all ask the same L2 lines at once.
     const int krot = blockIdx.x * 5;
@@ -225,11 +215,22 @@ __global__ void __launch_bounds__(256, TM <= 32 ? 4 : 2) k_gemm(GemmArgs p) {
       }
     }
   }
+}
 
+// KEEP: the finished values (through silu when keep_silu is set; zeros in rows past the end) also go, in the layout
+// of an A tile, to `keep`, which must not overlap `smem`: the next product of a chain takes them from there.
+template <int H, bool BF16, int TM, bool KEEP>
+__device__ __forceinline__ void gemm_epilogue(const GemmArgs& p, int cb, int grp, int rbeg, int rend,
+                                              f32x16_t (&acc)[GemmCfg<H, BF16, TM>::RB][GemmCfg<H, BF16, TM>::CB],
+                                              unsigned char* smem, unsigned char* keep, int keep_silu) {
+  using C = GemmCfg<H, BF16, TM>;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wr = wave / C::WC, wc = wave % C::WC;
   // ---- epilogue: the accumulators go through LDS, one 32-row block per wavefront row at a time, so that the
   // auxiliary operands and C are accessed row-major with 16-byte loads and stores (few, wide, whole cache lines)
   const bool use_bias = p.bias && ((p.bias_cb_mask >> cb) & 1);
   const bool pair_out = C::CB == 2 && ((p.pair_cb_mask >> cb) & 1);
+  const bool use_add = p.add1 && ((p.add1_cb_mask >> cb) & 1);
   constexpr int CH = H / 4;                 // 4-column chunks per row
   constexpr int PROWS = C::WR * 32;         // rows per pass
   constexpr int RSTEP = 256 / CH;           // rows swept by the 256 threads at once
@@ -293,7 +294,7 @@ __global__ void __launch_bounds__(256, TM <= 32 ? 4 : 2) k_gemm(GemmArgs p) {
 #pragma unroll
       for (int k = 0; k < NCH; ++k) {
         if (p.mul) mv[k] = *reinterpret_cast<const float4*>(p.mul + grow[k] * p.ldmul + gcol);
-        if (p.add1) a1[k] = *reinterpret_cast<const float4*>(p.add1 + grow[k] * p.ldadd1 + gcol);
+        if (use_add) a1[k] = *reinterpret_cast<const float4*>(p.add1 + grow[k] * p.ldadd1 + gcol);
         if (p.add2) a2[k] = *reinterpret_cast<const float4*>(p.add2 + grow[k] * p.ldadd2 + gcol);
       }
 #pragma unroll
@@ -308,11 +309,96 @@ __global__ void __launch_bounds__(256, TM <= 32 ? 4 : 2) k_gemm(GemmArgs p) {
             x.x *= mv[k].x; x.y *= mv[k].y; x.z *= mv[k].z; x.w *= mv[k].w;
           }
         }
-        if (p.add1) { x.x += a1[k].x; x.y += a1[k].y; x.z += a1[k].z; x.w += a1[k].w; }
+        if (use_add) { x.x += a1[k].x; x.y += a1[k].y; x.z += a1[k].z; x.w += a1[k].w; }
         if (p.add2) { x.x += a2[k].x; x.y += a2[k].y; x.z += a2[k].z; x.w += a2[k].w; }
         if (ok[k]) *reinterpret_cast<float4*>(p.C + grow[k] * p.ldc + gcol) = x;
+        if constexpr (KEEP) {
+          float4 y = x;
+          if (keep_silu) { y.x = silu_f(y.x); y.y = silu_f(y.y); y.z = silu_f(y.z); y.w = silu_f(y.w); }
+          if (!ok[k]) y = make_float4(0.f, 0.f, 0.f, 0.f);
+          const int trow = (sr / 32) * C::WROWS + i * 32 + (sr % 32);   // row of the tile
+          if (BF16) {
+            uint2 o;
+            o.x = pack_bf16x2(y.x, y.y);
+            o.y = pack_bf16x2(y.z, y.w);
+            *reinterpret_cast<uint2*>(keep + ((size_t)trow * C::STRIDE + q * 4) * 2) = o;
+          } else {
+            *reinterpret_cast<float4*>(keep + ((size_t)trow * C::STRIDE + q * 4) * 4) = y;
+          }
+        }
       }
     }
+  }
+}
+
+template <int H, bool BF16, int TM>
+__global__ void __launch_bounds__(256, TM <= 32 ? 4 : 2) k_gemm(GemmArgs p) {
+  using C = GemmCfg<H, BF16, TM>;
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int cb = blockIdx.y;
+  int grp = 0, rbeg, rend;
+  if (p.grp_ptr) {
+    if (!tile_of_group(p.grp_ptr, p.S, C::TM, blockIdx.x, grp, rbeg, rend)) return;
+  } else {
+    rbeg = blockIdx.x * C::TM;
+    rend = p.M;
+    if (rbeg >= rend) return;
+  }
+  f32x16_t acc[C::RB][C::CB];
+#pragma unroll
+  for (int i = 0; i < C::RB; ++i)
+#pragma unroll
+    for (int j = 0; j < C::CB; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+  for (int kc = 0; kc < p.nkc; ++kc) {
+    if (kc) __syncthreads();
+    gemm_stage_a<H, BF16, TM>(p, kc, rbeg, rend, smem);
+    __syncthreads();
+    gemm_multiply<H, BF16, TM>(p, kc, cb, grp, smem, acc);
+  }
+  gemm_epilogue<H, BF16, TM, false>(p, cb, grp, rbeg, rend, acc, smem, nullptr, 0);
+}
+
+// Two products in a row on one row tile, the second one taking the first one's finished tile from LDS as its A
+// operand (has_first), or only the second one with its A tile staged once for all of its column blocks: the rows
+// are read once and what lies between the two products never leaves the compute unit. LDS: [staging / epilogue |
+// the kept A tile]. No groups and no row indirection here.
+template <int H, bool BF16, int TM>
+__global__ void __launch_bounds__(256, 3) k_gemm_chain(GemmArgs p1, GemmArgs p2, int has_first, int keep_silu) {
+  using C = GemmCfg<H, BF16, TM>;
+  extern __shared__ __align__(16) unsigned char smem[];
+  unsigned char* keep = smem + C::LDS_BYTES;
+  const int rbeg = blockIdx.x * C::TM, rend = p2.M;
+  if (rbeg >= rend) return;
+  f32x16_t acc[C::RB][C::CB];
+  if (has_first) {
+#pragma unroll
+    for (int i = 0; i < C::RB; ++i)
+#pragma unroll
+      for (int j = 0; j < C::CB; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+    for (int kc = 0; kc < p1.nkc; ++kc) {
+      if (kc) __syncthreads();
+      gemm_stage_a<H, BF16, TM>(p1, kc, rbeg, rend, smem);
+      __syncthreads();
+      gemm_multiply<H, BF16, TM>(p1, kc, 0, 0, smem, acc);
+    }
+    gemm_epilogue<H, BF16, TM, true>(p1, 0, 0, rbeg, rend, acc, smem, keep, keep_silu);
+  } else {
+    gemm_stage_a<H, BF16, TM>(p2, 0, rbeg, rend, keep);
+  }
+  __syncthreads();
+  for (int cb = 0; cb < p2.ncb; ++cb) {
+#pragma unroll
+    for (int i = 0; i < C::RB; ++i)
+#pragma unroll
+      for (int j = 0; j < C::CB; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+    gemm_multiply<H, BF16, TM>(p2, 0, cb, 0, keep, acc);
+    gemm_epilogue<H, BF16, TM, false>(p2, cb, 0, rbeg, rend, acc, smem, nullptr, 0);
   }
 }
 
@@ -352,6 +438,51 @@ static int32_t launch_gemm_t(hipStream_t st, const GemmArgs& a) {
   if (a.M <= 0) return HGNN_OK;
   if constexpr (GemmCfg<H, BF16>::WR == 1) return launch_gemm_tm<H, BF16, 32>(st, a);
   else return launch_gemm_tm<H, BF16, 64>(st, a);
+}
+
+template <int H, bool BF16>
+static int32_t launch_gemm_chain_t(hipStream_t st, const GemmArgs* first, const GemmArgs& second, int keep_silu) {
+  constexpr int TM = GemmCfg<H, BF16>::WR == 1 ? 32 : 64;
+  using C = GemmCfg<H, BF16, TM>;
+  if (second.M <= 0) return HGNN_OK;
+  constexpr size_t LDS = C::LDS_BYTES + C::A_BYTES;
+  static bool raised = false;   // the kernel's LDS limit is raised once per variant
+  if (!raised) {
+    HGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_chain<H, BF16, TM>),
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS));
+    raised = true;
+  }
+  const int tiles = (second.M + TM - 1) / TM;
+  ProfScope ps(second.tag, st);
+  k_gemm_chain<H, BF16, TM><<<dim3(tiles), 256, LDS, st>>>(first ? *first : second, second, first ? 1 : 0, keep_silu);
+  HGNN_LAUNCH_CHECK("k_gemm_chain");
+  return HGNN_OK;
+}
+
+// `first` (optional): one column block, its finished tile (through silu when keep_silu) is the A operand of `second`,
+// whose own A fields are then ignored; without `first`, `second` runs alone with its A tile (one k chunk) staged
+// once for all its column blocks.
+int32_t launch_gemm_chain(hipStream_t st, int H, bool bf16, const GemmArgs* first, const GemmArgs& second, int keep_silu) {
+  for (const GemmArgs* g : {first, &second}) {
+    if (!g) continue;
+    HGNN_REQUIRE(!g->row_idx && !g->grp_ptr, HGNN_ERR_BAD_SHAPE, "gemm chain: no groups, no row indirection");
+    HGNN_REQUIRE(g->B && (g->C || g->Cpair), HGNN_ERR_NULLPTR, "gemm chain: null operand");
+    HGNN_REQUIRE(g->pair_cb_mask == 0 || (H == 256 && g->Cpair), HGNN_ERR_BAD_SHAPE, "gemm chain: pair output needs H = 256");
+  }
+  HGNN_REQUIRE(second.ncb >= 1 && second.ncb <= 2, HGNN_ERR_BAD_SHAPE, "gemm chain: bad chunk counts");
+  if (first) {
+    HGNN_REQUIRE(first->nkc >= 1 && first->nkc <= 2 && first->ncb == 1 && first->A[0] && first->pair_cb_mask == 0 &&
+                     first->M == second.M,
+                 HGNN_ERR_BAD_SHAPE, "gemm chain: bad first product");
+  } else {
+    HGNN_REQUIRE(second.nkc == 1 && second.A[0], HGNN_ERR_BAD_SHAPE, "gemm chain: the lone product takes one k chunk");
+  }
+  switch (H) {
+    case 64: return bf16 ? launch_gemm_chain_t<64, true>(st, first, second, keep_silu) : launch_gemm_chain_t<64, false>(st, first, second, keep_silu);
+    case 128: return bf16 ? launch_gemm_chain_t<128, true>(st, first, second, keep_silu) : launch_gemm_chain_t<128, false>(st, first, second, keep_silu);
+    case 256: return bf16 ? launch_gemm_chain_t<256, true>(st, first, second, keep_silu) : launch_gemm_chain_t<256, false>(st, first, second, keep_silu);
+  }
+  return set_error(HGNN_ERR_BAD_SHAPE, "H must be 64, 128 or 256 (got %d)", H);
 }
 
 int32_t launch_gemm(hipStream_t st, int H, bool bf16, const GemmArgs& a) {

@@ -178,10 +178,11 @@ static size_t unsaved_extra_bytes(int N, int64_t E, int H, bool bf16, int k) {
 // Packs its own weight blocks into w.packed: 0 W1a, 1 W1b, 2 W2, 3 W3a, 4 W3b, 5 W4.
 // keep_xe: also keep x_e = wx . m_e per edge (fused kernels only; the fragment path always does)
 // k == 1: `attr` is the single per-edge attribute (the squared length); k > 1: [E,k] attributes, bf16 operands
+// h_out (optional): also h' = h + silu(z3) W4 + b4, formed by the kernel that forms z3 while its tile is on the chip
 static int32_t layer_fwd_core(hipStream_t st, int32_t N, int64_t E, int32_t H, int32_t k, bool bf16, float alpha,
                               const int32_t* row_ptr, const int32_t* dst, const int32_t* col, const float* attr,
                               const float* rvec, const float* h_in, const float* v_in, const float* W, float* v_out,
-                              const LayerWs& w, const LayerSaved& s, bool keep_xe) {
+                              const LayerWs& w, const LayerSaved& s, bool keep_xe, float* h_out) {
   const LayerOff o(H, k);
   PackArgs pk;
   pk.src = W;
@@ -207,7 +208,7 @@ static int32_t layer_fwd_core(hipStream_t st, int32_t N, int64_t E, int32_t H, i
       g.Cpair = reinterpret_cast<unsigned*>(s.PQ); g.ldpair = H; g.pair_cb_mask = 3;
       g.pair_off[0] = 0; g.pair_off[1] = H / 2;
     }
-    HGNN_TRY(launch_gemm(st, H, bf16, g));
+    HGNN_TRY(launch_gemm_chain(st, H, bf16, nullptr, g, 0));   // h is staged once for both halves
   }
   {  // per edge: a1 = silu(P[dst] + Q[col] + d2*w1d), z2 = a1 W2 + b2   (one fused kernel)
     EdgeFwdArgs e;
@@ -229,7 +230,17 @@ static int32_t layer_fwd_core(hipStream_t st, int32_t N, int64_t E, int32_t H, i
     g.M = N;
     g.bias = W + o.b3; g.bias_cb_mask = 1;
     g.C = s.z3; g.ldc = H;
-    HGNN_TRY(launch_gemm(st, H, bf16, g));
+    if (h_out) {  // h' = h + silu(z3) W4 + b4 from the same tile
+      GemmArgs g2;
+      g2.B = w.packed; g2.blk[0][0] = 5;
+      g2.M = N;
+      g2.bias = W + o.b4; g2.bias_cb_mask = 1;
+      g2.add1 = h_in; g2.ldadd1 = H;
+      g2.C = h_out; g2.ldc = H;
+      HGNN_TRY(launch_gemm_chain(st, H, bf16, &g, g2, 1));
+    } else {
+      HGNN_TRY(launch_gemm(st, H, bf16, g));
+    }
   }
   return HGNN_OK;
 }
@@ -272,17 +283,7 @@ static int32_t mp_layer_fwd_impl(void* stream, int32_t N, int64_t E, int32_t H, 
   HGNN_REQUIRE(ws_bytes >= w.bytes, HGNN_ERR_WORKSPACE_TOO_SMALL, "mp_layer workspace: need %zu bytes, got %zu", w.bytes, ws_bytes);
   HGNN_REQUIRE(saved_bytes >= s.bytes, HGNN_ERR_WORKSPACE_TOO_SMALL, "mp_layer saved buffer: need %zu bytes, got %zu", s.bytes, saved_bytes);
   const LayerOff o(H, k);
-  HGNN_TRY(layer_fwd_core(st, N, E, H, k, bf16, alpha, row_ptr, dst, col, d2, rvec, h_in, v_in, W, v_out, w, s, keep_xe));
-  {  // h' = h + silu(z3) W4 + b4
-    GemmArgs g;
-    g.A[0] = s.z3; g.lda[0] = H; g.a_silu = 1;
-    g.B = w.packed; g.blk[0][0] = 5;
-    g.M = N;
-    g.bias = W + o.b4; g.bias_cb_mask = 1;
-    g.add1 = h_in; g.ldadd1 = H;
-    g.C = h_out; g.ldc = H;
-    HGNN_TRY(launch_gemm(st, H, bf16, g));
-  }
+  HGNN_TRY(layer_fwd_core(st, N, E, H, k, bf16, alpha, row_ptr, dst, col, d2, rvec, h_in, v_in, W, v_out, w, s, keep_xe, h_out));
   return HGNN_OK;
 }
 
@@ -347,7 +348,7 @@ static int32_t mp_layer_bwd_impl(void* stream, int32_t N, int64_t E, int32_t H, 
     // the forward pass of this layer once more, up to z3 (its v' goes to scratch; the input v does not matter for
     // anything the reverse pass reads, so any valid [N,3] array serves)
     float* v_scratch = reinterpret_cast<float*>(static_cast<char*>(const_cast<void*>(saved)) + s.bytes);
-    HGNN_TRY(layer_fwd_core(st, N, E, H, k, bf16, alpha, row_ptr, dst, col, d2, rvec, h_in, g_v_out, W, v_scratch, w, s, false));
+    HGNN_TRY(layer_fwd_core(st, N, E, H, k, bf16, alpha, row_ptr, dst, col, d2, rvec, h_in, g_v_out, W, v_scratch, w, s, false, nullptr));
   }
 
   // transposed blocks: 0 W4^T, 1 W3a^T, 2 W3b^T, 3 W2^T, 4 W1a^T, 5 W1b^T
@@ -379,14 +380,23 @@ static int32_t mp_layer_bwd_impl(void* stream, int32_t N, int64_t E, int32_t H, 
     a.colsum_dest[0] = gW + o.b4; a.colsum_partial = w.cs_partial;
     HGNN_TRY(launch_wgrad(sx, H, bf16, a));
   }
-  {  // g_z3 = (g_h' W4^T) * silu'(z3)
+  {  // g_z3 = (g_h' W4^T) * silu'(z3), and from the same tile [g_h' + g_h(a) | g_M] = g_z3 W3^T (+ g_h' on the first half)
     GemmArgs g;
     g.A[0] = g_h_out; g.lda[0] = H;
     g.B = w.packed; g.blk[0][0] = 0;
     g.M = N;
     g.mul = s.z3; g.ldmul = H; g.mul_is_z = 1;
     g.C = w.g_z3; g.ldc = H;
-    HGNN_TRY(launch_gemm(st, H, bf16, g));
+    GemmArgs g2;
+    g2.B = w.packed; g2.blk[0][0] = 1; g2.blk[0][1] = 2; g2.ncb = 2;
+    g2.M = N;
+    g2.add1 = g_h_out; g2.ldadd1 = H; g2.add1_cb_mask = 1;
+    g2.C = w.g_hM; g2.ldc = 2 * H;
+    if (edge_pairs(H, bf16)) {   // the g_M half goes out as bf16 pairs for the fused edge kernel
+      g2.Cpair = w.gM_pk; g2.ldpair = H / 2; g2.pair_cb_mask = 2; g2.pair_off[1] = 0;
+      g2.pair_scale = alpha;   // the pair form carries alpha * g_M
+    }
+    HGNN_TRY(launch_gemm_chain(st, H, bf16, &g, g2, 0));
   }
   HGNN_TRY(stream_after(sx, st, ss.ev[1]));
   {  // side: gW3 = [h ; M]^T g_z3 ; gb3
@@ -398,18 +408,6 @@ static int32_t mp_layer_bwd_impl(void* stream, int32_t N, int64_t E, int32_t H, 
     a.partial = w.partial2;
     a.colsum_dest[0] = gW + o.b3; a.colsum_partial = w.cs_partial;
     HGNN_TRY(launch_wgrad(sx, H, bf16, a));
-  }
-  {  // [g_h(a) | g_M] = g_z3 W3^T
-    GemmArgs g;
-    g.A[0] = w.g_z3; g.lda[0] = H;
-    g.B = w.packed; g.blk[0][0] = 1; g.blk[0][1] = 2; g.ncb = 2;
-    g.M = N;
-    g.C = w.g_hM; g.ldc = 2 * H;
-    if (edge_pairs(H, bf16)) {   // the g_M half goes out as bf16 pairs for the fused edge kernel
-      g.Cpair = w.gM_pk; g.ldpair = H / 2; g.pair_cb_mask = 2; g.pair_off[1] = 0;
-      g.pair_scale = alpha;   // the pair form carries alpha * g_M
-    }
-    HGNN_TRY(launch_gemm(st, H, bf16, g));
   }
   // edge part: c_e, then g_z2 -> (x W2^T) -> g_z1 with the per-column sums. The fused edge kernel fills
   // every CU by itself, so the side stream is drained first instead of competing with it.
@@ -464,13 +462,12 @@ static int32_t mp_layer_bwd_impl(void* stream, int32_t N, int64_t E, int32_t H, 
     a.colsum_dest[0] = gW + o.b1; a.colsum_partial = w.cs_partial;
     HGNN_TRY(launch_wgrad(sx, H, bf16, a));
   }
-  {  // g_h = g_h' + g_h(a) + g_P W1a^T + g_Q W1b^T
+  {  // g_h = (g_h' + g_h(a)) + g_P W1a^T + g_Q W1b^T
     GemmArgs g;
     g.A[0] = w.g_PQ; g.lda[0] = 2 * H; g.A[1] = w.g_PQ + H; g.lda[1] = 2 * H; g.nkc = 2;
     g.B = w.packed; g.blk[0][0] = 4; g.blk[1][0] = 5;
     g.M = N;
-    g.add1 = g_h_out; g.ldadd1 = H;
-    g.add2 = w.g_hM; g.ldadd2 = 2 * H;
+    g.add1 = w.g_hM; g.ldadd1 = 2 * H;
     g.C = g_h_in; g.ldc = H;
     HGNN_TRY(launch_gemm(st, H, bf16, g));
   }
