@@ -64,10 +64,15 @@ def kernel_work(tag, N, E, H, dtype):
 
 def roofline_of(tag, avg_s, N, E, H, dtype, traffic=None):
     flops, nbytes = kernel_work(tag, N, E, H, dtype)
-    t_mfma = flops / (PEAK_TFLOPS[dtype] * 1e12)
+    mfma_dtype = dtype
+    if dtype == "f32" and tag in ("edge_fused_fwd", "edge_fused_bwd", "wgrad_edge"):
+        # fp32 operands of the per-edge products are split into three bf16 terms each: six bf16 products on the
+        # matrix cores per fp32 product; the executed bf16 flops are what is held against the bf16 peak
+        flops, mfma_dtype = 6.0 * flops, "bf16"
+    t_mfma = flops / (PEAK_TFLOPS[mfma_dtype] * 1e12)
     t_hbm = nbytes / (PEAK_HBM_GBS * 1e9)
     if t_mfma > t_hbm:
-        ach, peak, unit, bound, work = flops / avg_s / 1e12, PEAK_TFLOPS[dtype], "TFLOP/s", "mfma", flops
+        ach, peak, unit, bound, work = flops / avg_s / 1e12, PEAK_TFLOPS[mfma_dtype], "TFLOP/s", "mfma", flops
     else:
         ach, peak, unit, bound, work = nbytes / avg_s / 1e9, PEAK_HBM_GBS, "GB/s", "hbm", nbytes
     return {"kernel": tag, "bound": bound, "achieved": ach, "peak": peak, "unit": unit, "frac": ach / peak,

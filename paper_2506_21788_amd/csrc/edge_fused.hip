@@ -136,24 +136,28 @@ __device__ __forceinline__ void tile_mma(const unsigned char* smem, const void* 
 #pragma unroll 4
     for (int kb = 4; kb < NKB; ++kb) step(kb, std::false_type{});
   } else {
-    constexpr int NKB = H / 8;
+    // fp32 operands: the A tile stays fp32 in LDS and is split into three bf16 terms as it is read; B comes as
+    // three bf16 planes (launch_pack_x3); six bf16 products per step of 16 k (see split_bf16x3)
+    constexpr int NKB = H / 16;
+    constexpr size_t PLANE = (size_t)H * H * 2;
     auto step = [&](int kb, auto first) {
-      float4 a[C::RB];
+      bf16x8_t a[C::RB][3];
 #pragma unroll
       for (int i = 0; i < C::RB; ++i) {
         const int row = (wr * C::RB + i) * 32 + (lane & 31);
-        a[i] = *reinterpret_cast<const float4*>(smem + ((size_t)row * C::STRIDE + kb * 8 + (lane >> 5) * 4) * 4);
+        const float* ap = reinterpret_cast<const float*>(smem) + (size_t)row * C::STRIDE + kb * 16 + (lane >> 5) * 8;
+        const float4 lo = *reinterpret_cast<const float4*>(ap), hi = *reinterpret_cast<const float4*>(ap + 4);
+        const float x[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+        split_bf16x3(x, a[i]);
       }
 #pragma unroll
       for (int j = 0; j < C::CB; ++j) {
-        const float4 b = ldg_at<float4>(uoff(Bpacked, (size_t)((wc * C::CB + j) * NKB + kb) * 1024), lane * 16u);
+        bf16x8_t b[3];
 #pragma unroll
-        for (int i = 0; i < C::RB; ++i) {
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].x, b.x, decltype(first)::value ? zero : acc[i][j], 0, 0, 0);
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].y, b.y, acc[i][j], 0, 0, 0);
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].z, b.z, acc[i][j], 0, 0, 0);
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].w, b.w, acc[i][j], 0, 0, 0);
-        }
+        for (int q = 0; q < 3; ++q)
+          b[q] = ldg_at<bf16x8_t>(uoff(Bpacked, q * PLANE + (size_t)((wc * C::CB + j) * NKB + kb) * 1024), lane * 16u);
+#pragma unroll
+        for (int i = 0; i < C::RB; ++i) acc[i][j] = mfma_bf16x3(a[i], b, decltype(first)::value ? zero : acc[i][j]);
       }
     };
     static_assert(NKB % 4 == 0, "steps are taken four at a time");
@@ -564,7 +568,7 @@ __global__ void __launch_bounds__(256, 2) k_edge_fwd(EdgeFwdArgs p, int ntiles) 
   using C = ECfg<H, BF16>;
   static_assert(!ATTR || (BF16 && C::TM == 64), "edge attributes: bf16 operands, 64-edge tiles");
   // keep this wavefront's slice of W2 in registers? (not with attributes: their accumulators need the room)
-  constexpr bool BRES = BRES_REQ && (BF16 || H <= 128) && !ATTR;
+  constexpr bool BRES = BRES_REQ && BF16 && !ATTR;   // fp32 operands take W2 as three bf16 planes from L2
   extern __shared__ __align__(16) unsigned char smem[];
   int* sc = reinterpret_cast<int*>(smem + C::LDS_BYTES);   // [2][3][TM] per-edge scalars, double buffered
   unsigned short* atb = reinterpret_cast<unsigned short*>(smem + C::LDS_BYTES + 6 * C::TM * 4);   // [2][ATTR_TILE] (ATTR)
@@ -1588,25 +1592,40 @@ k_wgrad_frag(int64_t nblk32, const void* __restrict__ a1_pk, const void* __restr
     HGNN_WG_PIPELINE
 #undef HGNN_WG_MMA
   } else {
+    // fp32 operands: two chunks of four edges make one step of the bf16 matrix cores (eight edges per lane, the
+    // same eight for both operands); both operands are split into three bf16 terms on the way (split_bf16x3).
+    // Four chunks per block, so every trip of the loop is full.
     const f32x4_t* __restrict__ A = reinterpret_cast<const f32x4_t*>(a1_pk);
     const f32x4_t* __restrict__ B = reinterpret_cast<const f32x4_t*>(gz2_pk);
     f32x4_t a0[NBW], b0[NBW], a1[NBW], b1[NBW], a2[NBW], b2[NBW], a3[NBW], b3[NBW];
-#define HGNN_WG_MMA(a, b, valid)                                                                       \
+#define HGNN_WG_MMA2(ax, bx, ay, by)                                                                   \
   {                                                                                                    \
-    const bool ok_ = (valid);                                                                          \
-    const f32x4_t zero_ = {0.f, 0.f, 0.f, 0.f};                                                        \
+    bf16x8_t as_[NBW][3], bs_[NBW][3];                                                                 \
     _Pragma("unroll") for (int i = 0; i < NBW; ++i) {                                                  \
-      const f32x4_t az_ = ok_ ? a[i] : zero_;                                                          \
-      _Pragma("unroll") for (int j = 0; j < NBW; ++j) {                                                \
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(az_[0], b[j][0], acc[i][j], 0, 0, 0);         \
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(az_[1], b[j][1], acc[i][j], 0, 0, 0);         \
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(az_[2], b[j][2], acc[i][j], 0, 0, 0);         \
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(az_[3], b[j][3], acc[i][j], 0, 0, 0);         \
-      }                                                                                                \
+      const float xa_[8] = {ax[i][0], ax[i][1], ax[i][2], ax[i][3], ay[i][0], ay[i][1], ay[i][2], ay[i][3]}; \
+      const float xb_[8] = {bx[i][0], bx[i][1], bx[i][2], bx[i][3], by[i][0], by[i][1], by[i][2], by[i][3]}; \
+      split_bf16x3(xa_, as_[i]);                                                                       \
+      split_bf16x3(xb_, bs_[i]);                                                                       \
     }                                                                                                  \
+    _Pragma("unroll") for (int i = 0; i < NBW; ++i)                                                    \
+      _Pragma("unroll") for (int j = 0; j < NBW; ++j) acc[i][j] = mfma_bf16x3(as_[i], bs_[j], acc[i][j]); \
   }
-    HGNN_WG_PIPELINE
-#undef HGNN_WG_MMA
+    // (eight chunk buffers instead of four, i.e. three pairs of loads in flight, measured no faster)
+    if (nchunk > 0) {
+      HGNN_WG_LOAD(0, a0, b0)
+      HGNN_WG_LOAD(1, a1, b1)
+      HGNN_WG_LOAD(2, a2, b2)
+      HGNN_WG_LOAD(3, a3, b3)
+      for (int64_t c = 0; c < nchunk; c += 4) {
+        HGNN_WG_MMA2(a0, b0, a1, b1)
+        HGNN_WG_LOAD(HGNN_WG_CL(c + 4), a0, b0)
+        HGNN_WG_LOAD(HGNN_WG_CL(c + 5), a1, b1)
+        HGNN_WG_MMA2(a2, b2, a3, b3)
+        HGNN_WG_LOAD(HGNN_WG_CL(c + 6), a2, b2)
+        HGNN_WG_LOAD(HGNN_WG_CL(c + 7), a3, b3)
+      }
+    }
+#undef HGNN_WG_MMA2
   }
 #undef HGNN_WG_LOAD
 #undef HGNN_WG_PIPELINE

@@ -63,6 +63,7 @@ static LayerSaved carve_saved(void* p, int N, int64_t E, int H, bool bf16, int k
 
 struct LayerWs {
   void* packed;    // 6 blocks
+  void* packed_x3; // fp32 operands: W2 (forward) or W2^T (reverse) as three bf16 planes for the fused edge kernels
   void* gz2_pk;    // [E32,H] operand-packed
   void* gz1_vm;    // [E32,H] v-major (bf16 or fp32)
   float* cvec;     // [E]
@@ -81,6 +82,7 @@ static LayerWs carve_ws(void* p, int N, int64_t E, int H, bool bf16, int k = 1) 
   Carver c(p);
   LayerWs w;
   w.packed = c.take<char>(6 * packed_block_bytes(H, bf16));
+  w.packed_x3 = bf16 ? nullptr : c.take<char>(packed_x3_bytes(H));
   w.gz2_pk = c.take<char>(frag_rows(E) * H * (bf16 ? 2 : 4));
   w.gz1_vm = c.take<char>(frag_rows(E) * H * (bf16 ? 2 : 4));
   w.cvec = c.take<float>((size_t)E + 4);
@@ -217,6 +219,10 @@ static int32_t layer_fwd_core(hipStream_t st, int32_t N, int64_t E, int32_t H, i
     else e.d2 = attr;
     e.PQ = s.PQ; e.w1d = W + o.W1 + 2 * HH;
     e.W2p = static_cast<const char*>(w.packed) + 2 * packed_block_bytes(H, bf16);
+    if (!bf16) {
+      HGNN_TRY(launch_pack_x3(st, H, W, PackDesc{o.W2, H, 1}, w.packed_x3));
+      e.W2p = w.packed_x3;
+    }
     e.b2 = W + o.b2;
     e.a1_pk = s.a1_pk; e.z2_vm = s.z2_vm;
     HGNN_TRY(launch_edge_fwd(st, H, bf16, e));
@@ -424,6 +430,10 @@ static int32_t mp_layer_bwd_impl(void* stream, int32_t N, int64_t E, int32_t H, 
     }
     e.PQ = s.PQ; e.w1d = W + o.W1 + 2 * HH;
     e.W2Tp = static_cast<const char*>(w.packed) + 3 * packed_block_bytes(H, bf16);
+    if (!bf16) {
+      HGNN_TRY(launch_pack_x3(st, H, W, PackDesc{o.W2, 1, H}, w.packed_x3));
+      e.W2Tp = w.packed_x3;
+    }
     e.z2_vm = s.z2_vm;
     if (edge_pairs(H, bf16)) { e.gM = w.gM_pk; e.ldgM = H / 2; }
     else { e.gM = w.g_hM + H; e.ldgM = 2 * H; }
