@@ -148,11 +148,14 @@ int32_t hgnn_embed_bwd_static(void* stream, int32_t N, int32_t H, const int32_t*
  * N * 2H * 4 bytes reaches 4 GiB (the edge kernels index edges and gathered rows with 32 bits);
  * WORKSPACE_TOO_SMALL if ws / saved are smaller than the query says; UNIMPLEMENTED if saved == NULL at another
  * width.
- * _bwd also enqueues weight-gradient work on a stream the library creates once (default priority). It
+ * _bwd may enqueue weight-gradient work on a stream the library creates once (default priority). It
  * forks from and joins `stream` through events inside the call, so for the caller everything is
  * ordered on `stream`; the call that creates that stream must not run under stream capture.
- * hgnn_set_side_stream(0) (or the environment variable HGNN_SIDE_STREAM=0 before the first call) keeps all
- * work on `stream`, e.g. to time kernels in isolation; it returns the previous setting (0 / 1).
+ * hgnn_set_side_stream(enable): 1 = always use that stream, 0 = keep all work on `stream` (e.g. to time kernels
+ * in isolation), -1 = the library's choice (the default: used at widths other than 64 / 128 / 256, where many small
+ * atom-level launches leave compute units idle, not used by the fused kernels, which fill the chip by themselves).
+ * The environment variable HGNN_SIDE_STREAM = 0 / 1, read before the first call, sets the same. Returns the previous
+ * setting (-1 / 0 / 1). The results do not depend on it bit for bit.
  * The library keeps per-process state without locks: call it from one host thread at a time.
  * ------------------------------------------------------------------------------------------- */
 int32_t hgnn_set_side_stream(int32_t enable);

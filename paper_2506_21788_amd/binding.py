@@ -109,10 +109,11 @@ def version() -> int:
     return int(_lib.hgnn_version())
 
 
-def set_side_stream(enable: bool) -> bool:
-    """Weight gradients of the layer's reverse pass on the library's side stream (default) or not; returns the
-    previous setting."""
-    return bool(_lib.hgnn_set_side_stream(C.c_int32(1 if enable else 0)))
+def set_side_stream(enable):
+    """Weight gradients of the layer's reverse pass on the library's side stream (True), on the caller's stream
+    (False), or wherever the library chooses per code path (None, the default); returns the previous setting."""
+    prev = int(_lib.hgnn_set_side_stream(C.c_int32(-1 if enable is None else (1 if enable else 0))))
+    return None if prev < 0 else bool(prev)
 
 
 def _check(code):

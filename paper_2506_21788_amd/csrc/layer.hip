@@ -120,14 +120,23 @@ int32_t stream_after(hipStream_t to, hipStream_t from, hipEvent_t ev) {
   return HGNN_OK;
 }
 
-// -1: not decided yet (then the environment variable HGNN_SIDE_STREAM decides: "0" = off); 0 / 1: set by the caller
-static int g_side_mode = -1;
-bool side_stream_enabled() {
-  if (g_side_mode < 0) {
+// -2: not read yet (then the environment variable HGNN_SIDE_STREAM decides: "0" = off, "1" = on, anything else or
+// unset = the library's choice); -1: the library's choice; 0 / 1: set by the caller.
+// The library's choice: on for the fragment path (its many atom-level launches leave compute units idle that the
+// weight gradients fill: config 6 13.18 against 13.31 ms per step), off for the fused kernels, every one of which
+// fills the chip by itself (config 1 0.93 against 1.03 ms, config 5 32.2 against 32.6 ms, configs 2-4 the same
+// either way).
+static int g_side_mode = -2;
+static int side_setting() {
+  if (g_side_mode == -2) {
     const char* e = getenv("HGNN_SIDE_STREAM");
-    g_side_mode = (e && e[0] == '0') ? 0 : 1;
+    g_side_mode = (e && e[0] == '0') ? 0 : ((e && e[0] == '1') ? 1 : -1);
   }
-  return g_side_mode != 0;
+  return g_side_mode;
+}
+bool side_stream_enabled(bool fragment_path) {
+  const int s = side_setting();
+  return s < 0 ? fragment_path : s != 0;
 }
 
 static int32_t check_layer_args(int N, int64_t E, int H, int dtype) {
@@ -148,8 +157,8 @@ static int32_t check_layer_args(int N, int64_t E, int H, int dtype) {
 using namespace hgnn;
 
 extern "C" int32_t hgnn_set_side_stream(int32_t enable) {
-  const int32_t before = side_stream_enabled() ? 1 : 0;
-  g_side_mode = enable ? 1 : 0;
+  const int32_t before = side_setting();
+  g_side_mode = enable < 0 ? -1 : (enable ? 1 : 0);
   return before;
 }
 
@@ -372,7 +381,7 @@ static int32_t mp_layer_bwd_impl(void* stream, int32_t N, int64_t E, int32_t H, 
 
   SideStream& ss = side_stream();
   HGNN_REQUIRE(ss.ok, HGNN_ERR_HIP, "could not create the side stream");
-  hipStream_t sx = side_stream_enabled() ? ss.s : st;
+  hipStream_t sx = side_stream_enabled(false) ? ss.s : st;
   HGNN_TRY(stream_after(sx, st, ss.ev[0]));   // inputs of this call are ready on the side stream too
 
   // every gradient field is written below even when there is nothing to sum over

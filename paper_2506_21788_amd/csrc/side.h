@@ -12,7 +12,7 @@ struct SideStream {
   bool ok = false;
 };
 SideStream& side_stream();          // created on first use (default priority, non-blocking)
-bool side_stream_enabled();         // hgnn_set_side_stream / HGNN_SIDE_STREAM
+bool side_stream_enabled(bool fragment_path);   // hgnn_set_side_stream / HGNN_SIDE_STREAM, else the library's choice per path
 int32_t stream_after(hipStream_t to, hipStream_t from, hipEvent_t ev);   // `to` waits for what `from` holds so far
 
 }  // namespace hgnn

@@ -1490,7 +1490,7 @@ int32_t wide_layer_bwd(hipStream_t st, const WideLayerArgs& a) {
   // from and joins the caller's stream through events. Buffers read on sx are written once per call on st.
   SideStream& ss = side_stream();
   HGNN_REQUIRE(ss.ok, HGNN_ERR_HIP, "could not create the side stream");
-  hipStream_t sx = side_stream_enabled() ? ss.s : st;
+  hipStream_t sx = side_stream_enabled(true) ? ss.s : st;
   {  // g_h' as R and T ([h ; M] and silu(z3) were left as T fragments by the forward pass)
     ToFragArgs u;
     u.X = a.g_h_out; u.ldx = H; u.M = d.N; u.Mp = d.Np; u.ncol = H; u.Cp = Hp;
