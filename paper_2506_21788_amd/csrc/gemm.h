@@ -21,13 +21,15 @@ struct PackArgs {
   void* dst;  // block b goes to dst + b*H*H elements
   int nblocks;
   PackDesc d[MAX_PACK];
+  // optional (fp32 packing only): one more block, d[x3_desc], also as three bf16 planes of H*H elements each
+  // (hi, mid, lo: the block is their sum), every plane in the bf16 B-operand order: what the fused edge kernels
+  // multiply with when the operands are fp32
+  void* x3_dst = nullptr;
+  int x3_desc = 0;
 };
 int32_t launch_pack(hipStream_t st, int H, bool bf16, const PackArgs& a, int groups = 1, long src_grp_stride = 0,
                     long dst_grp_stride_elems = 0);
 inline size_t packed_block_bytes(int H, bool bf16) { return (size_t)H * H * (bf16 ? 2 : 4); }
-// One fp32 block as three bf16 planes of H*H elements each (hi, mid, lo: the block is their sum), every plane in the
-// bf16 B-operand order: what the fused edge kernels multiply with when the operands are fp32.
-int32_t launch_pack_x3(hipStream_t st, int H, const float* src, const PackDesc& d, void* dst);
 inline size_t packed_x3_bytes(int H) { return (size_t)H * H * 6; }
 
 // ---- row-tile GEMM --------------------------------------------------------------------------

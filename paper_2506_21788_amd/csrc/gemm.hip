@@ -26,6 +26,22 @@ __global__ void k_pack(PackArgs a, int H, long src_grp_stride, long dst_grp_stri
   const int grp = blockIdx.z;
   const int idx = blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= H * H) return;
+  if (b == a.nblocks) {   // the extra block as three bf16 planes (see split_bf16x3), each in the bf16 operand order
+    const PackDesc d = a.d[a.x3_desc];
+    const int t = idx & 7, lane = (idx >> 3) & 63, kb = (idx >> 9) % (H / 16), nb = (idx >> 9) / (H / 16);
+    const int n = nb * 32 + (lane & 31);
+    const int k = kb * 16 + (lane >> 5) * 8 + t;
+    const float v = a.src[d.src_off + (long)k * d.sk + (long)n * d.sn];
+    const unsigned h = f2bf_bits(v);
+    const float r = v - __uint_as_float(h << 16);
+    const unsigned m = f2bf_bits(r);
+    const float q = r - __uint_as_float(m << 16);
+    unsigned short* dst = static_cast<unsigned short*>(a.x3_dst);
+    dst[idx] = (unsigned short)h;
+    dst[(long)H * H + idx] = (unsigned short)m;
+    dst[2L * H * H + idx] = (unsigned short)f2bf_bits(q);
+    return;
+  }
   const PackDesc d = a.d[b];
   const float* src = a.src + grp * src_grp_stride + d.src_off;
   int n, k;
@@ -51,35 +67,11 @@ int32_t launch_pack(hipStream_t st, int H, bool bf16, const PackArgs& a, int gro
                     long dst_grp_stride_elems) {
   if (a.nblocks <= 0 || groups <= 0) return HGNN_OK;
   ProfScope ps(PT_PACK, st);
-  dim3 grid((H * H + 255) / 256, a.nblocks, groups);
+  const bool x3 = a.x3_dst != nullptr && !bf16 && groups == 1;
+  dim3 grid((H * H + 255) / 256, a.nblocks + (x3 ? 1 : 0), groups);
   if (bf16) k_pack<true><<<grid, 256, 0, st>>>(a, H, src_grp_stride, dst_grp_stride_elems);
   else k_pack<false><<<grid, 256, 0, st>>>(a, H, src_grp_stride, dst_grp_stride_elems);
   HGNN_LAUNCH_CHECK("k_pack");
-  return HGNN_OK;
-}
-
-// One fp32 block as three bf16 planes (see split_bf16x3), each in the bf16 B-operand order: plane q at
-// dst + q*H*H elements.
-__global__ void k_pack_x3(const float* __restrict__ src, PackDesc d, unsigned short* __restrict__ dst, int H) {
-  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx >= H * H) return;
-  const int t = idx & 7, lane = (idx >> 3) & 63, kb = (idx >> 9) % (H / 16), nb = (idx >> 9) / (H / 16);
-  const int n = nb * 32 + (lane & 31);
-  const int k = kb * 16 + (lane >> 5) * 8 + t;
-  const float v = src[d.src_off + (long)k * d.sk + (long)n * d.sn];
-  const unsigned h = f2bf_bits(v);
-  const float r = v - __uint_as_float(h << 16);
-  const unsigned m = f2bf_bits(r);
-  const float q = r - __uint_as_float(m << 16);
-  dst[idx] = (unsigned short)h;
-  dst[(long)H * H + idx] = (unsigned short)m;
-  dst[2L * H * H + idx] = (unsigned short)f2bf_bits(q);
-}
-
-int32_t launch_pack_x3(hipStream_t st, int H, const float* src, const PackDesc& d, void* dst) {
-  ProfScope ps(PT_PACK, st);
-  k_pack_x3<<<dim3((H * H + 255) / 256), 256, 0, st>>>(src, d, static_cast<unsigned short*>(dst), H);
-  HGNN_LAUNCH_CHECK("k_pack_x3");
   return HGNN_OK;
 }
 

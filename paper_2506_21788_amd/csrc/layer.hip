@@ -206,6 +206,7 @@ static int32_t layer_fwd_core(hipStream_t st, int32_t N, int64_t E, int32_t H, i
   pk.d[3] = {o.W3, H, 1};
   pk.d[4] = {o.W3 + HH, H, 1};
   pk.d[5] = {o.W4, H, 1};
+  pk.x3_dst = w.packed_x3; pk.x3_desc = 2;   // fp32 operands: W2 also as three bf16 planes
   HGNN_TRY(launch_pack(st, H, bf16, pk));
 
   {  // P | Q
@@ -228,10 +229,7 @@ static int32_t layer_fwd_core(hipStream_t st, int32_t N, int64_t E, int32_t H, i
     else e.d2 = attr;
     e.PQ = s.PQ; e.w1d = W + o.W1 + 2 * HH;
     e.W2p = static_cast<const char*>(w.packed) + 2 * packed_block_bytes(H, bf16);
-    if (!bf16) {
-      HGNN_TRY(launch_pack_x3(st, H, W, PackDesc{o.W2, H, 1}, w.packed_x3));
-      e.W2p = w.packed_x3;
-    }
+    if (!bf16) e.W2p = w.packed_x3;
     e.b2 = W + o.b2;
     e.a1_pk = s.a1_pk; e.z2_vm = s.z2_vm;
     HGNN_TRY(launch_edge_fwd(st, H, bf16, e));
@@ -377,6 +375,7 @@ static int32_t mp_layer_bwd_impl(void* stream, int32_t N, int64_t E, int32_t H, 
   pk.d[3] = {o.W2, 1, H};
   pk.d[4] = {o.W1, 1, H};
   pk.d[5] = {o.W1 + HH, 1, H};
+  pk.x3_dst = w.packed_x3; pk.x3_desc = 3;   // fp32 operands: W2^T also as three bf16 planes
   HGNN_TRY(launch_pack(st, H, bf16, pk));
 
   SideStream& ss = side_stream();
@@ -439,10 +438,7 @@ static int32_t mp_layer_bwd_impl(void* stream, int32_t N, int64_t E, int32_t H, 
     }
     e.PQ = s.PQ; e.w1d = W + o.W1 + 2 * HH;
     e.W2Tp = static_cast<const char*>(w.packed) + 3 * packed_block_bytes(H, bf16);
-    if (!bf16) {
-      HGNN_TRY(launch_pack_x3(st, H, W, PackDesc{o.W2, 1, H}, w.packed_x3));
-      e.W2Tp = w.packed_x3;
-    }
+    if (!bf16) e.W2Tp = w.packed_x3;
     e.z2_vm = s.z2_vm;
     if (edge_pairs(H, bf16)) { e.gM = w.gM_pk; e.ldgM = H / 2; }
     else { e.gM = w.g_hM + H; e.ldgM = 2 * H; }
