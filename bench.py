@@ -29,7 +29,8 @@ def kernel_work(tag, N, E, H, dtype):
     tensors it gathers counted once (compulsory traffic; re-reads are cache traffic)."""
     b = 2 if dtype == "bf16" else 4
     EH, NH = float(E) * H, float(N) * H
-    pairs = dtype == "bf16" and H == 256   # a1 is recomputed in the reverse pass instead of stored
+    # a1 is recomputed by the W2-gradient kernel instead of stored: bf16 pairs (H = 256), fp32 operands at H = 128
+    pairs = (dtype == "bf16" and H == 256) or (dtype == "f32" and H == 128)
     if tag == "edge_fused_fwd":      # out: z2 (and a1 unless recomputed); in: dst, col, d2; gathers P|Q
         return 2.0 * EH * H, (1 if pairs else 2) * EH * b + 12.0 * E + 2 * NH * b
     if tag == "edge_fused_bwd":      # in: z2, dst, col, d2, c; out: g_z2, g_z1; gathers P|Q, g_M

@@ -96,6 +96,11 @@ int32_t launch_wgrad_frag_recompute(hipStream_t st, int H, int64_t E, const int3
                                     const float* d2, const void* PQ, const float* w1d, const void* gz2_pk,
                                     float* partial, float* gW2);
 
+// The same for fp32 operands at H = 128 (PQ: [N, 2H] fp32); see a1_recomputed() in layer.hip for where it is used.
+int32_t launch_wgrad_frag_recompute32(hipStream_t st, int H, int64_t E, const int32_t* dst, const int32_t* col,
+                                      const float* d2, const float* PQ, const float* w1d, const void* gz2_pk,
+                                      float* partial, float* gW2);
+
 // out[i, 0..H) (row pitch ldo) = sum over t in ptr[i]:ptr[i+1] of X[perm ? perm[t] : t, :], X v-major (bf16 or
 // fp32), accumulated in fp32
 // dot (optional): [E] out, dot[e] = sum_c wdot[c] X[e][c] for every edge of the list

@@ -1831,6 +1831,187 @@ __global__ void __launch_bounds__(512) k_wgrad_frag_rc(WgradRcArgs p) {
       }
 }
 
+// The recomputing weight gradient for fp32 operands at H = 128: the same scheme with four wavefronts (2 x 2 blocks
+// of the 128 x 128 accumulator each, two workgroups per compute unit). Every value is split into its three bf16
+// terms (split_bf16x3) once, by the wavefront that produces it, and the LDS stages hold three planes of ready
+// operands; the consumers take six products per block pair. A producer wavefront forms silu(z1) for 64 columns and
+// eight of a chunk's sixteen edges; it also splits one column block of the chunk's g_z2 (two 16-byte pieces per
+// lane, already in operand order) into the stage. Two stages, one barrier per chunk.
+struct WgradRc32Args {
+  int64_t nblk32;
+  int E;
+  const int32_t *dst, *col;
+  const float* d2;
+  const float* PQ;      // [N, 2H] fp32: P | Q
+  const float* w1d;
+  const void* gz2_pk;   // fp32, operand-packed; rows past the last edge of the last block hold zeros
+  float* partial;
+};
+
+template <int H>
+__global__ void __launch_bounds__(256, 2) k_wgrad_frag_rc32(WgradRc32Args p) {
+  constexpr int NCB = H / 32;
+  constexpr int PLANE = NCB * 1024;   // one bf16 plane of the four operand blocks of a chunk: [block][64 slots][8 bf16]
+  constexpr int STAGE = 3 * PLANE;
+  static_assert(H == 128, "four wavefronts, 2 x 2 blocks each");
+  using PQP = PQPitch<H, false>;
+  typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
+  __shared__ __align__(16) unsigned char stage_a[2 * STAGE];
+  __shared__ __align__(16) unsigned char stage_b[2 * STAGE];
+  const int lane = threadIdx.x & 63;
+  const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+  const int x = lane & 31;
+  // as a producer: columns wcc * 64 + lane (block 2 wcc + (lane >> 5)), edges 8 hh .. 8 hh + 7 of the chunk: edge
+  // 8 hh + j is element 4 hh + (j & 3) of operand lane group j >> 2
+  const int wcc = w >> 1, hh = w & 1;
+  // as a consumer: A blocks 2 wa, 2 wa + 1; g_z2 blocks 2 wb, 2 wb + 1
+  const int wa = w >> 1, wb = w & 1;
+  f32x16_t acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+  const float w1 = p.w1d[wcc * 64 + lane];
+  const int G = gridDim.x, bid = blockIdx.x;
+  const int nblk = (int)p.nblk32;
+  const int E = p.E;
+  int bfirst, bstride, nmine;   // this workgroup's blocks, by XCD as in the bf16-pair kernel
+  if ((G & 7) == 0) {
+    const int xcd = bid & 7, r = bid >> 3;
+    bstride = G >> 3;
+    const int lo = (int)((int64_t)nblk * xcd / 8), hi = (int)((int64_t)nblk * (xcd + 1) / 8);
+    nmine = hi - lo > r ? (hi - lo - r + bstride - 1) / bstride : 0;
+    bfirst = lo + r;
+  } else {
+    bstride = G;
+    nmine = nblk > bid ? (nblk - bid + G - 1) / G : 0;
+    bfirst = bid;
+  }
+  const int nchunk = nmine * 2;   // two 16-edge chunks per 32-edge block
+  const unsigned colb = (unsigned)(wcc * 64 + lane) * 4u;
+  // lanes 0..7 fetch dst, 8..15 col, 16..23 d2 of the wavefront's eight edges
+  const int32_t* const idx_arr = lane < 8 ? p.dst : (lane < 16 ? p.col : reinterpret_cast<const int32_t*>(p.d2));
+  unsigned char* const a_out = stage_a + (2 * wcc + (lane >> 5)) * 1024 + x * 16 + 8 * hh;
+
+  auto chunk_blk = [&](int c) { const int cc = c < nchunk ? c : nchunk - 1; return bfirst + (cc >> 1) * bstride; };
+  auto chunk_half = [&](int c) { const int cc = c < nchunk ? c : nchunk - 1; return cc & 1; };
+  auto load_iv = [&](int c, int& iv) {
+    const int e = chunk_blk(c) * 32 + chunk_half(c) * 16 + 8 * hh + (lane & 7);
+    iv = 0;
+    if (lane < 24 && e < E) iv = idx_arr[e];   // past the last edge: row 0 (always valid), and g_z2 is zero there
+  };
+  auto gather = [&](const int iv, float (&vp)[8], float (&vq)[8]) {
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const unsigned rd = (unsigned)__builtin_amdgcn_readlane(iv, u), rc = (unsigned)__builtin_amdgcn_readlane(iv, 8 + u);
+      vp[u] = ldg_f32(uoff(p.PQ, rd * PQP::ROW), colb);
+      vq[u] = ldg_f32(uoff(p.PQ, rc * PQP::ROW + PQP::QOFF), colb);
+    }
+  };
+  // this wavefront's column block (w) of the chunk's g_z2: the two pieces are elements 0..3 and 4..7 of every slot
+  auto load_b = [&](int c, f32x4_t (&b)[2]) {
+    const char* src = uoff(p.gz2_pk, (((size_t)chunk_blk(c) * NCB + w) * 4 + 2 * chunk_half(c)) * 1024);
+#pragma unroll
+    for (int s = 0; s < 2; ++s) b[s] = ldg_nt<f32x4_t>(src + s * 1024, lane * 16u);
+  };
+  auto stage_b_put = [&](int st, const f32x4_t (&b)[2]) {
+    const float xs[8] = {b[0][0], b[0][1], b[0][2], b[0][3], b[1][0], b[1][1], b[1][2], b[1][3]};
+    bf16x8_t o[3];
+    split_bf16x3(xs, o);
+#pragma unroll
+    for (int q = 0; q < 3; ++q)
+      *reinterpret_cast<bf16x8_t*>(stage_b + st * STAGE + q * PLANE + w * 1024 + lane * 16) = o[q];
+  };
+  auto stage_a_put = [&](int c, int st, const float (&vp)[8], const float (&vq)[8], const int iv) {
+    const float keep = c < nchunk ? 1.f : 0.f;   // uniform over the workgroup; chunks past the end give zeros
+    float v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const float d = __int_as_float(__builtin_amdgcn_readlane(iv, 16 + u));
+      v[u] = silu_f(vp[u] + vq[u] + d * w1) * keep;
+    }
+    bf16x8_t o[3];
+    split_bf16x3(v, o);
+#pragma unroll
+    for (int q = 0; q < 3; ++q) {
+      const u32x4_t wv = __builtin_bit_cast(u32x4_t, o[q]);
+      unsigned char* dstp = a_out + st * STAGE + q * PLANE;
+      *reinterpret_cast<uint2*>(dstp) = make_uint2(wv[0], wv[1]);         // edges 8 hh + 0..3: lane group 0
+      *reinterpret_cast<uint2*>(dstp + 512) = make_uint2(wv[2], wv[3]);   // edges 8 hh + 4..7: lane group 1
+    }
+  };
+  auto mma = [&](int st) {
+    bf16x8_t a[2][3], b[2][3];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int q = 0; q < 3; ++q)
+        a[i][q] = *reinterpret_cast<const bf16x8_t*>(stage_a + st * STAGE + q * PLANE + (2 * wa + i) * 1024 + lane * 16);
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int q = 0; q < 3; ++q)
+        b[j][q] = *reinterpret_cast<const bf16x8_t*>(stage_b + st * STAGE + q * PLANE + (2 * wb + j) * 1024 + lane * 16);
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) acc[i][j] = mfma_bf16x3(a[i], b[j], acc[i][j]);
+  };
+
+  if (nchunk > 0) {   // uniform over the workgroup
+    int iv[8];                    // index ring: slot = chunk mod 8
+    float vp[4][8], vq[4][8];     // gather ring: slot = chunk mod 4
+    f32x4_t bb[4][2];             // g_z2 load ring: slot = chunk mod 4
+    // prologue: indices of chunks 0..8, g_z2 and gathers of chunks 0..4, chunk 0 staged
+#pragma unroll
+    for (int k = 0; k < 8; ++k) load_iv(k, iv[k]);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) load_b(k, bb[k]);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) gather(iv[k], vp[k], vq[k]);
+    stage_b_put(0, bb[0]);
+    stage_a_put(0, 0, vp[0], vq[0], iv[0]);
+    load_b(4, bb[0]);   // chunk 4 takes the ring slots chunk 0 has just left
+    gather(iv[4], vp[0], vq[0]);
+    load_iv(8, iv[0]);
+    __syncthreads();
+    for (int c = 0; c < nchunk; c += 8) {
+      // step for chunk j = c + k: multiply chunk j out of its stage and form and stage chunk j + 1; then ask for the
+      // g_z2 and the gathers of chunk j + 5 (ring slots of chunk j + 1, just emptied) and the indices of chunk j + 9
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        mma(k & 1);
+        stage_b_put((k + 1) & 1, bb[(k + 1) & 3]);
+        stage_a_put(c + k + 1, (k + 1) & 1, vp[(k + 1) & 3], vq[(k + 1) & 3], iv[(k + 1) & 7]);
+        load_b(c + k + 5, bb[(k + 1) & 3]);
+        gather(iv[(k + 5) & 7], vp[(k + 1) & 3], vq[(k + 1) & 3]);
+        load_iv(c + k + 9, iv[(k + 1) & 7]);
+        // one matrix product, then a share of the vector work: the products of a step run behind its sigmoids and
+        // splits instead of blocking both wavefronts of the SIMD
+#pragma unroll
+        for (int i = 0; i < 24; ++i) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x002, 10, 0);
+        }
+        __syncthreads();
+      }
+    }
+  }
+  float* out = p.partial + (size_t)blockIdx.x * H * H;
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int k1 = (2 * wa + i) * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+        const int k2 = (2 * wb + j) * 32 + (lane & 31);
+        out[k1 * H + k2] = acc[i][j][v];
+      }
+}
+
 // most workgroups (= partial H x H results) of one launch: the partial buffer holds 32 Mi floats at every H
 constexpr int WGRAD_FRAG_MAX_GRID = 512;                        // at H = 256
 static int wgrad_frag_max_grid(int H) { return WGRAD_FRAG_MAX_GRID * (256 / H) * (256 / H); }
@@ -1888,6 +2069,31 @@ int32_t launch_wgrad_frag_recompute(hipStream_t st, int H, int64_t E, const int3
     ProfScope ps(PT_WGRAD_EDGE, st);
     k_wgrad_frag_rc<256><<<dim3((unsigned)grid), 512, 0, st>>>(a);
     HGNN_LAUNCH_CHECK("k_wgrad_frag_rc");
+  }
+  float* dest[4] = {gW2, nullptr, nullptr, nullptr};
+  return launch_reduce_partials(st, partial, (int)grid, 1, (long)H * H, dest, 1, 0);
+}
+
+int32_t launch_wgrad_frag_recompute32(hipStream_t st, int H, int64_t E, const int32_t* dst, const int32_t* col,
+                                      const float* d2, const float* PQ, const float* w1d, const void* gz2_pk,
+                                      float* partial, float* gW2) {
+  HGNN_REQUIRE(H == 128, HGNN_ERR_BAD_SHAPE, "the recomputing fp32 weight-gradient kernel exists at H = 128");
+  HGNN_REQUIRE(E >= 0 && E <= EDGE_MAX_E, HGNN_ERR_BAD_SHAPE, "edge kernels index edges with 32 bits (E = %lld)",
+               (long long)E);
+  // two workgroups per compute unit, each leaving one partial; fewer when there are fewer than two blocks for each
+  const int64_t nblk32 = (E + 31) / 32;
+  int64_t grid = 2 * (int64_t)num_cus();
+  if (grid > wgrad_frag_max_grid(H)) grid = wgrad_frag_max_grid(H);
+  if (grid > (nblk32 + 1) / 2) grid = (nblk32 + 1) / 2;
+  if (grid >= 8) grid &= ~(int64_t)7;
+  if (grid < 1) grid = 1;
+  WgradRc32Args a;
+  a.nblk32 = nblk32; a.E = (int)E; a.dst = dst; a.col = col; a.d2 = d2; a.PQ = PQ; a.w1d = w1d;
+  a.gz2_pk = gz2_pk; a.partial = partial;
+  {
+    ProfScope ps(PT_WGRAD_EDGE, st);
+    k_wgrad_frag_rc32<128><<<dim3((unsigned)grid), 256, 0, st>>>(a);
+    HGNN_LAUNCH_CHECK("k_wgrad_frag_rc32");
   }
   float* dest[4] = {gW2, nullptr, nullptr, nullptr};
   return launch_reduce_partials(st, partial, (int)grid, 1, (long)H * H, dest, 1, 0);

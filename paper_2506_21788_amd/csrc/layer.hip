@@ -45,7 +45,9 @@ struct LayerSaved {
 };
 
 // a1 is recomputed (not stored) where the weight-gradient kernel can rebuild it from the gathers alone
-static bool a1_recomputed(int H, bool bf16, int k) { return edge_pairs(H, bf16) && k == 1; }
+// a1 = silu(z1) is not stored but recomputed by the W2-gradient kernel: bf16 pairs (H = 256), and fp32 operands at
+// H = 128, with the squared length as the only edge attribute
+static bool a1_recomputed(int H, bool bf16, int k) { return (edge_pairs(H, bf16) || (!bf16 && H == 128)) && k == 1; }
 
 static LayerSaved carve_saved(void* p, int N, int64_t E, int H, bool bf16, int k = 1) {
   Carver c(p);
@@ -450,7 +452,10 @@ static int32_t mp_layer_bwd_impl(void* stream, int32_t N, int64_t E, int32_t H, 
   }
   HGNN_TRY(stream_after(sx, st, ss.ev[2]));
   // side: g_W2 = a1^T g_z2 streams while the main stream runs the two segment sums
-  if (a1_recomputed(H, bf16, k))
+  if (a1_recomputed(H, bf16, k) && !bf16)
+    HGNN_TRY(launch_wgrad_frag_recompute32(sx, H, E, dst, col, d2, reinterpret_cast<const float*>(s.PQ),
+                                           W + o.W1 + 2 * HH, w.gz2_pk, w.partial2, gW + o.W2));
+  else if (a1_recomputed(H, bf16, k))
     HGNN_TRY(launch_wgrad_frag_recompute(sx, H, E, dst, col, d2, s.PQ, W + o.W1 + 2 * HH, w.gz2_pk, w.partial2,
                                          gW + o.W2));
   else
