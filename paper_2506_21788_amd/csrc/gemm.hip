@@ -754,7 +754,7 @@ __global__ void __launch_bounds__(256) k_wgrad(WgradArgs p, int nsplit, int rows
 }
 
 int wgrad_splits(int64_t M) {
-  int64_t s = (M + 255) / 256;   // about 256 rows per split: enough workgroups to fill the chip at N ~ 10^4..10^5
+  int64_t s = (M + 63) / 64;   // about 64 rows per split (two steps): short chains when there are few atoms
   if (s < 1) s = 1;
   if (s > 160) s = 160;
   return (int)s;
