@@ -116,7 +116,14 @@ def test_layer_other_modes_edge_counts(H, dtype, E):
     _run_layer(N=300, E=E, H=H, dtype=dtype, seed=E)
 
 
-# Atom counts around the split rules of the atom-level weight gradients (about 256 rows per split, at most one round
+# fp32 operands at H = 128: the W2 gradient recomputes a1 in a kernel of its own (two 16-edge chunks per 32-edge block,
+# eight-chunk trips, grids rounded to multiples of eight workgroups, one ragged block at most)
+@pytest.mark.parametrize("E", [0, 1, 15, 16, 17, 31, 32, 33, 255, 256, 257, 511, 16385, 3 * 16384 + 45])
+def test_layer_f32_128_edge_counts(E):
+    _run_layer(N=500, E=E, H=128, dtype="f32", seed=E + 7)
+
+
+# Atom counts around the split rules of the atom-level weight gradients (about 64 rows per split, at most one round
 # of resident workgroups, whole workgroups per compute unit, a grid padded to groups of eight splits) and the row
 # tiles of the atom-level products; few edges, so that the atom-level kernels decide the outcome.
 @pytest.mark.parametrize("H,dtype,N", [(256, "bf16", 1), (256, "bf16", 255), (256, "bf16", 257), (256, "bf16", 2049),
