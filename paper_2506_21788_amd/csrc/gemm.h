@@ -98,7 +98,12 @@ struct WgradArgs {
   float* colsum_partial = nullptr;   // scratch, wgrad_colsum_partial_floats()
   int tag = PT_WGRAD_NODE;
 };
-size_t wgrad_colsum_partial_floats(int H, int64_t M);
+size_t wgrad_colsum_partial_floats(int H, int64_t M);   // room for the column sums of four B operands
+// Up to three such products over the same rows in ONE launch (no groups, no row indirection): every job keeps its own
+// operands and destinations; `partial` and `colsum_partial` of job 0 serve all of them and must hold
+// wgrad_partial_floats(H, M, total blocks, 1) and wgrad_colsum_partial_floats(H, M) floats. At most 8 blocks and 4
+// B operands in total.
+int32_t launch_wgrad_multi(hipStream_t st, int H, bool bf16, const WgradArgs* jobs, int njobs);
 int wgrad_splits(int64_t M);
 size_t wgrad_partial_floats(int H, int64_t M, int nblocks, int S);
 int32_t launch_wgrad(hipStream_t st, int H, bool bf16, const WgradArgs& a);

@@ -522,7 +522,7 @@ struct ReduceArgs {
   int nsplit;
   int nblk;
   long blk_elems;
-  float* dest[4];
+  float* dest[8];
   long grp_dest_stride;
 };
 
@@ -576,14 +576,20 @@ __global__ void __launch_bounds__(256) k_reduce_partials_tall(ReduceArgs a) {
   if (ph == 0 && i < a.blk_elems) a.dest[blk][grp * a.grp_dest_stride + i] = ((sh[e] + sh[64 + e]) + sh[128 + e]) + sh[192 + e];
 }
 
+static int32_t launch_reduce_partials_n(hipStream_t st, const float* partial, int nsplit, int nblk, long blk_elems,
+                                         float* const* dest, int ndest, int groups, long grp_dest_stride);
 int32_t launch_reduce_partials(hipStream_t st, const float* partial, int nsplit, int nblk, long blk_elems,
                                float* const dest[4], int groups, long grp_dest_stride) {
+  return launch_reduce_partials_n(st, partial, nsplit, nblk, blk_elems, dest, 4, groups, grp_dest_stride);
+}
+static int32_t launch_reduce_partials_n(hipStream_t st, const float* partial, int nsplit, int nblk, long blk_elems,
+                                         float* const* dest, int ndest, int groups, long grp_dest_stride) {
   ReduceArgs r;
   r.partial = partial;
   r.nsplit = nsplit;
   r.nblk = nblk;
   r.blk_elems = blk_elems;
-  for (int i = 0; i < 4; ++i) r.dest[i] = dest[i];
+  for (int i = 0; i < 8; ++i) r.dest[i] = i < ndest ? dest[i] : nullptr;
   r.grp_dest_stride = grp_dest_stride;
   if (blk_elems <= 1024 && nsplit >= 64)
     k_reduce_partials_tall<<<dim3((unsigned)((blk_elems + 63) / 64), nblk, groups), 256, 0, st>>>(r);
@@ -607,8 +613,18 @@ struct WgradCfg {
   static constexpr int TILES = H / OT;
 };
 
+// the jobs of one launch: their output tiles are numbered one job after the other (ny_off), so are their blocks in
+// the partial buffer (blk_off) and their B operands in the column-sum partials (cs_off)
+struct WgradJobs {
+  WgradArgs job[3];
+  int njobs;
+  int ny_off[4], blk_off[4], cs_off[4];
+  float* partial;
+  float* colsum_partial;
+};
+
 template <int H, bool BF16>
-__global__ void __launch_bounds__(256) k_wgrad(WgradArgs p, int nsplit, int rows_per_split, int ny) {
+__global__ void __launch_bounds__(256) k_wgrad(WgradJobs m, int nsplit, int rows_per_split, int ny) {
   using C = WgradCfg<H>;
   __shared__ __align__(16) float sA[WG_RC * C::STRIDE];
   __shared__ __align__(16) float sB[WG_RC * C::STRIDE];
@@ -621,6 +637,11 @@ __global__ void __launch_bounds__(256) k_wgrad(WgradArgs p, int nsplit, int rows
   const int split = (place / ny) * 8 + xcd, grp = blockIdx.z;
   if (split >= nsplit) return;   // uniform over the workgroup (the grid is padded to whole groups of 8 splits)
   int y = place % ny;
+  int jb = 0;   // uniform over the workgroup
+  if (m.njobs > 1 && y >= m.ny_off[1]) jb = 1;
+  if (m.njobs > 2 && y >= m.ny_off[2]) jb = 2;
+  y -= m.ny_off[jb];
+  const WgradArgs& p = m.job[jb];
   const int tb = y % C::TILES; y /= C::TILES;
   const int ta = y % C::TILES; y /= C::TILES;
   const int ib = y % p.nB;
@@ -661,7 +682,7 @@ __global__ void __launch_bounds__(256) k_wgrad(WgradArgs p, int nsplit, int rows
   };
   // column sums of this workgroup's B tile ride along where they are asked for (one workgroup per B tile: the
   // one of the first A block and the first A tile); a thread's chunk column is the same at every step
-  const bool do_cs = p.colsum_partial != nullptr && ia == 0 && ta == 0;
+  const bool do_cs = m.colsum_partial != nullptr && (p.colsum_dest[0] || p.colsum_dest[1]) && ia == 0 && ta == 0;
   static_assert(256 % CH == 0, "a thread keeps its chunk column over the steps");
   float4 cs = make_float4(0.f, 0.f, 0.f, 0.f);
   if (rbeg < rend) fetch(rbeg);
@@ -736,11 +757,11 @@ __global__ void __launch_bounds__(256) k_wgrad(WgradArgs p, int nsplit, int rows
         const float4 t = sh[k * CH + tid];
         s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
       }
-      *reinterpret_cast<float4*>(p.colsum_partial + (((long)grp * nsplit + split) * p.nB + ib) * H + tb * C::OT + tid * 4) = s;
+      *reinterpret_cast<float4*>(m.colsum_partial + (((long)grp * nsplit + split) * m.cs_off[m.njobs] + m.cs_off[jb] + ib) * H + tb * C::OT + tid * 4) = s;
     }
   }
-  const int nblk = p.nA * p.nB;
-  float* out = p.partial + (((long)grp * nsplit + split) * nblk + blkid) * (long)(H * H);
+  const int nblk = m.blk_off[m.njobs];
+  float* out = m.partial + (((long)grp * nsplit + split) * nblk + m.blk_off[jb] + blkid) * (long)(H * H);
 #pragma unroll
   for (int i = 0; i < C::NB; ++i)
 #pragma unroll
@@ -760,7 +781,7 @@ int wgrad_splits(int64_t M) {
   return (int)s;
 }
 
-size_t wgrad_colsum_partial_floats(int H, int64_t M) { return (size_t)wgrad_splits(M) * 2 * H; }
+size_t wgrad_colsum_partial_floats(int H, int64_t M) { return (size_t)wgrad_splits(M) * 4 * H; }
 
 size_t wgrad_partial_floats(int H, int64_t M, int nblocks, int S) {
   return (size_t)wgrad_splits(M) * nblocks * S * H * H;
@@ -781,11 +802,25 @@ static int wgrad_resident_wgs() {
 }
 
 template <int H, bool BF16>
-static int32_t launch_wgrad_t(hipStream_t st, const WgradArgs& a) {
+static int32_t launch_wgrad_t(hipStream_t st, const WgradArgs* jobs, int njobs) {
   using C = WgradCfg<H>;
-  const int nblk = a.nA * a.nB;
+  const WgradArgs& a = jobs[0];
+  WgradJobs m;
+  m.njobs = njobs;
+  m.partial = a.partial;
+  m.colsum_partial = nullptr;
+  m.ny_off[0] = m.blk_off[0] = m.cs_off[0] = 0;
+  for (int j = 0; j < njobs; ++j) {
+    m.job[j] = jobs[j];
+    m.ny_off[j + 1] = m.ny_off[j] + jobs[j].nA * jobs[j].nB * C::TILES * C::TILES;
+    m.blk_off[j + 1] = m.blk_off[j] + jobs[j].nA * jobs[j].nB;
+    m.cs_off[j + 1] = m.cs_off[j] + jobs[j].nB;
+    if (jobs[j].colsum_dest[0] || jobs[j].colsum_dest[1]) m.colsum_partial = a.colsum_partial;
+  }
+  for (int j = njobs; j < 3; ++j) m.ny_off[j + 1] = m.blk_off[j + 1] = m.cs_off[j + 1] = 0;
+  const int nblk = m.blk_off[njobs];
   const int groups = a.grp_ptr ? a.S : 1;
-  const int ny = nblk * C::TILES * C::TILES;
+  const int ny = m.ny_off[njobs];
   // Splits: never more than the workspace was sized for; at most one round of resident workgroups (a second,
   // partly filled round costs a whole one); and below that a whole number of workgroups per CU, so that no CU
   // carries two while its neighbour carries one. Fewer splits also mean fewer partials to write and add up.
@@ -803,27 +838,45 @@ static int32_t launch_wgrad_t(hipStream_t st, const WgradArgs& a) {
   rps = (rps + WG_RC - 1) / WG_RC * WG_RC;
   if (rps < WG_RC) rps = WG_RC;
   ProfScope ps(a.tag, st);
-  k_wgrad<H, BF16><<<dim3((unsigned)((nsplit + 7) / 8 * 8 * ny), 1, groups), 256, 0, st>>>(a, nsplit, (int)rps, ny);
+  k_wgrad<H, BF16><<<dim3((unsigned)((nsplit + 7) / 8 * 8 * ny), 1, groups), 256, 0, st>>>(m, nsplit, (int)rps, ny);
   HGNN_LAUNCH_CHECK("k_wgrad");
-  HGNN_TRY(launch_reduce_partials(st, a.partial, nsplit, nblk, (long)H * H, a.dest, groups, a.grp_dest_stride));
-  if (a.colsum_partial) {
-    float* cd[4] = {a.colsum_dest[0], a.colsum_dest[1], nullptr, nullptr};
-    HGNN_TRY(launch_reduce_partials(st, a.colsum_partial, nsplit, a.nB, H, cd, 1, 0));
+  float* dest[8] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+  float* cd[4] = {nullptr, nullptr, nullptr, nullptr};
+  for (int j = 0; j < njobs; ++j) {
+    for (int b = 0; b < jobs[j].nA * jobs[j].nB; ++b) dest[m.blk_off[j] + b] = jobs[j].dest[b];
+    for (int b = 0; b < jobs[j].nB; ++b) cd[m.cs_off[j] + b] = jobs[j].colsum_dest[b];
   }
+  HGNN_TRY(launch_reduce_partials_n(st, m.partial, nsplit, nblk, (long)H * H, dest, 8, groups, a.grp_dest_stride));
+  if (m.colsum_partial) HGNN_TRY(launch_reduce_partials_n(st, m.colsum_partial, nsplit, m.cs_off[njobs], H, cd, 4, 1, 0));
   return HGNN_OK;
 }
 
-int32_t launch_wgrad(hipStream_t st, int H, bool bf16, const WgradArgs& a) {
-  HGNN_REQUIRE(a.nA >= 1 && a.nB >= 1 && a.nA * a.nB <= 4, HGNN_ERR_BAD_SHAPE, "wgrad: bad block counts");
-  HGNN_REQUIRE(a.A[0] && a.B[0] && a.partial && a.dest[0], HGNN_ERR_NULLPTR, "wgrad: null operand");
-  HGNN_REQUIRE(!a.colsum_partial || !a.grp_ptr, HGNN_ERR_BAD_SHAPE, "wgrad: column sums are not available per group");
+int32_t launch_wgrad_multi(hipStream_t st, int H, bool bf16, const WgradArgs* jobs, int njobs) {
+  HGNN_REQUIRE(jobs && njobs >= 1 && njobs <= 3, HGNN_ERR_BAD_SHAPE, "wgrad: one to three jobs");
+  int blocks = 0, nb = 0;
+  for (int j = 0; j < njobs; ++j) {
+    const WgradArgs& a = jobs[j];
+    HGNN_REQUIRE(a.nA >= 1 && a.nB >= 1 && a.nA * a.nB <= 4, HGNN_ERR_BAD_SHAPE, "wgrad: bad block counts");
+    HGNN_REQUIRE(a.A[0] && a.B[0] && a.dest[0], HGNN_ERR_NULLPTR, "wgrad: null operand");
+    HGNN_REQUIRE(!(a.colsum_dest[0] || a.colsum_dest[1]) || jobs[0].colsum_partial, HGNN_ERR_NULLPTR, "wgrad: no room for the column sums");
+    HGNN_REQUIRE(njobs == 1 || (!a.grp_ptr && !a.row_idx && a.M == jobs[0].M), HGNN_ERR_BAD_SHAPE,
+                 "wgrad: several jobs share their rows (no groups, no row indirection)");
+    blocks += a.nA * a.nB;
+    nb += a.nB;
+  }
+  HGNN_REQUIRE(jobs[0].partial, HGNN_ERR_NULLPTR, "wgrad: null partial buffer");
+  HGNN_REQUIRE(blocks <= 8 && nb <= 4, HGNN_ERR_BAD_SHAPE, "wgrad: too many blocks in one launch");
+  HGNN_REQUIRE(!(jobs[0].colsum_partial && (jobs[0].colsum_dest[0] || jobs[0].colsum_dest[1])) || !jobs[0].grp_ptr,
+               HGNN_ERR_BAD_SHAPE, "wgrad: column sums are not available per group");
   switch (H) {
-    case 64: return bf16 ? launch_wgrad_t<64, true>(st, a) : launch_wgrad_t<64, false>(st, a);
-    case 128: return bf16 ? launch_wgrad_t<128, true>(st, a) : launch_wgrad_t<128, false>(st, a);
-    case 256: return bf16 ? launch_wgrad_t<256, true>(st, a) : launch_wgrad_t<256, false>(st, a);
+    case 64: return bf16 ? launch_wgrad_t<64, true>(st, jobs, njobs) : launch_wgrad_t<64, false>(st, jobs, njobs);
+    case 128: return bf16 ? launch_wgrad_t<128, true>(st, jobs, njobs) : launch_wgrad_t<128, false>(st, jobs, njobs);
+    case 256: return bf16 ? launch_wgrad_t<256, true>(st, jobs, njobs) : launch_wgrad_t<256, false>(st, jobs, njobs);
   }
   return set_error(HGNN_ERR_BAD_SHAPE, "H must be 64, 128 or 256 (got %d)", H);
 }
+
+int32_t launch_wgrad(hipStream_t st, int H, bool bf16, const WgradArgs& a) { return launch_wgrad_multi(st, H, bf16, &a, 1); }
 
 // ---------------------------------------------------------------------------------------------
 // column sums

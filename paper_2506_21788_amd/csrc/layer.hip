@@ -92,7 +92,7 @@ static LayerWs carve_ws(void* p, int N, int64_t E, int H, bool bf16, int k = 1) 
   w.g_hM = c.take<float>((size_t)N * 2 * H);
   w.gM_pk = c.take<unsigned>((size_t)N * (H / 2));
   w.g_PQ = c.take<float>((size_t)N * 2 * H);
-  size_t pf = wgrad_partial_floats(H, N, 2, 1);
+  size_t pf = wgrad_partial_floats(H, N, 5, 1);   // the layer's five atom-level weight-gradient blocks in one launch
   const size_t cands[3] = {colsum_partial_floats(H, N, 1), wgrad_frag_partial_floats(H), edge_bwd_colpart_floats(H)};
   for (size_t x : cands) pf = x > pf ? x : pf;
   w.partial = c.take<float>(pf);
@@ -386,16 +386,6 @@ static int32_t mp_layer_bwd_impl(void* stream, int32_t N, int64_t E, int32_t H, 
   HGNN_TRY(stream_after(sx, st, ss.ev[0]));   // inputs of this call are ready on the side stream too
 
   // every gradient field is written below even when there is nothing to sum over
-  {  // side: gW4 = silu(z3)^T g_h' ; gb4 = column sums of g_h' (taken by the same kernel)   (inputs only)
-    WgradArgs a;
-    a.A[0] = s.z3; a.lda[0] = H; a.a_silu = 1;
-    a.B[0] = g_h_out; a.ldb[0] = H;
-    a.M = N;
-    a.dest[0] = gW + o.W4;
-    a.partial = w.partial2;
-    a.colsum_dest[0] = gW + o.b4; a.colsum_partial = w.cs_partial;
-    HGNN_TRY(launch_wgrad(sx, H, bf16, a));
-  }
   {  // g_z3 = (g_h' W4^T) * silu'(z3), and from the same tile [g_h' + g_h(a) | g_M] = g_z3 W3^T (+ g_h' on the first half)
     GemmArgs g;
     g.A[0] = g_h_out; g.lda[0] = H;
@@ -413,17 +403,6 @@ static int32_t mp_layer_bwd_impl(void* stream, int32_t N, int64_t E, int32_t H, 
       g2.pair_scale = alpha;   // the pair form carries alpha * g_M
     }
     HGNN_TRY(launch_gemm_chain(st, H, bf16, &g, g2, 0));
-  }
-  HGNN_TRY(stream_after(sx, st, ss.ev[1]));
-  {  // side: gW3 = [h ; M]^T g_z3 ; gb3
-    WgradArgs a;
-    a.A[0] = h_in; a.lda[0] = H; a.A[1] = s.M; a.lda[1] = H; a.nA = 2;
-    a.B[0] = w.g_z3; a.ldb[0] = H;
-    a.M = N;
-    a.dest[0] = gW + o.W3; a.dest[1] = gW + o.W3 + HH;
-    a.partial = w.partial2;
-    a.colsum_dest[0] = gW + o.b3; a.colsum_partial = w.cs_partial;
-    HGNN_TRY(launch_wgrad(sx, H, bf16, a));
   }
   // edge part: c_e, then g_z2 -> (x W2^T) -> g_z1 with the per-column sums. The fused edge kernel fills
   // every CU by itself, so the side stream is drained first instead of competing with it.
@@ -471,17 +450,6 @@ static int32_t mp_layer_bwd_impl(void* stream, int32_t N, int64_t E, int32_t H, 
   }
   if (g_rvec) HGNN_TRY(launch_edge_grvec(st, E, dst, s.xe, g_v_out, alpha, g_rvec));
   HGNN_TRY(launch_segsum_vm(st, H, bf16, N, colT_ptr, permT, w.gz1_vm, w.g_PQ + H, 2 * H, PT_SEGSUM_SRC));  // g_Q
-  HGNN_TRY(stream_after(sx, st, ss.ev[3]));
-  {  // side: gW1a = h^T g_P ; gW1b = h^T g_Q ; gb1 = sum_i g_P_i (column sums of the first B operand)
-    WgradArgs a;
-    a.A[0] = h_in; a.lda[0] = H;
-    a.B[0] = w.g_PQ; a.ldb[0] = 2 * H; a.B[1] = w.g_PQ + H; a.ldb[1] = 2 * H; a.nB = 2;
-    a.M = N;
-    a.dest[0] = gW + o.W1; a.dest[1] = gW + o.W1 + HH;
-    a.partial = w.partial2;
-    a.colsum_dest[0] = gW + o.b1; a.colsum_partial = w.cs_partial;
-    HGNN_TRY(launch_wgrad(sx, H, bf16, a));
-  }
   {  // g_h = (g_h' + g_h(a)) + g_P W1a^T + g_Q W1b^T
     GemmArgs g;
     g.A[0] = w.g_PQ; g.lda[0] = 2 * H; g.A[1] = w.g_PQ + H; g.lda[1] = 2 * H; g.nkc = 2;
@@ -490,6 +458,26 @@ static int32_t mp_layer_bwd_impl(void* stream, int32_t N, int64_t E, int32_t H, 
     g.add1 = w.g_hM; g.ldadd1 = 2 * H;
     g.C = g_h_in; g.ldc = H;
     HGNN_TRY(launch_gemm(st, H, bf16, g));
+  }
+  {  // the three atom-level weight gradients of the layer and their bias sums in one launch, once all their operands
+     // exist: gW4 = silu(z3)^T g_h', gb4 | gW3 = [h ; M]^T g_z3, gb3 | gW1a = h^T g_P, gW1b = h^T g_Q, gb1 = sum_i g_P_i
+    HGNN_TRY(stream_after(sx, st, ss.ev[3]));
+    WgradArgs j[3];
+    j[0].A[0] = s.z3; j[0].lda[0] = H; j[0].a_silu = 1;
+    j[0].B[0] = g_h_out; j[0].ldb[0] = H;
+    j[0].dest[0] = gW + o.W4;
+    j[0].colsum_dest[0] = gW + o.b4;
+    j[1].A[0] = h_in; j[1].lda[0] = H; j[1].A[1] = s.M; j[1].lda[1] = H; j[1].nA = 2;
+    j[1].B[0] = w.g_z3; j[1].ldb[0] = H;
+    j[1].dest[0] = gW + o.W3; j[1].dest[1] = gW + o.W3 + HH;
+    j[1].colsum_dest[0] = gW + o.b3;
+    j[2].A[0] = h_in; j[2].lda[0] = H;
+    j[2].B[0] = w.g_PQ; j[2].ldb[0] = 2 * H; j[2].B[1] = w.g_PQ + H; j[2].ldb[1] = 2 * H; j[2].nB = 2;
+    j[2].dest[0] = gW + o.W1; j[2].dest[1] = gW + o.W1 + HH;
+    j[2].colsum_dest[0] = gW + o.b1;
+    for (auto& a : j) a.M = N;
+    j[0].partial = w.partial2; j[0].colsum_partial = w.cs_partial;
+    HGNN_TRY(launch_wgrad_multi(sx, H, bf16, j, 3));
   }
   HGNN_TRY(stream_after(st, sx, ss.ev[4]));   // join: the caller's stream now also orders after every gradient
   if (g_v_in != g_v_out) HGNN_TRY(launch_copy_f32(st, g_v_out, g_v_in, (int64_t)N * 3));
