@@ -37,29 +37,38 @@ __global__ void k_embed_fwd(int N, int H, const int32_t* __restrict__ Z, const f
 // summed in order by a second kernel
 constexpr int EMB_CHUNK = 2048;
 
-__global__ void __launch_bounds__(256)
+// (1024 threads: the common species of a chunk have a thousand rows, which the row phases walk one after the other)
+__global__ void __launch_bounds__(1024)
 k_embed_bwd_part(int N, int H, const int32_t* __restrict__ Z, const float* __restrict__ g_h,
                  float* __restrict__ part /*[nchunk][ZMAX+1][H]*/) {
-  __shared__ float4 sh[256];
+  __shared__ float4 sh[1024];
   const int z = blockIdx.x, chunk = blockIdx.y;
   const int CH = H >> 2;
-  const int q = threadIdx.x % CH, ph = threadIdx.x / CH, nph = 256 / CH;
+  const int q = threadIdx.x % CH, ph = threadIdx.x / CH, nph = 1024 / CH;
   const int lo = chunk * EMB_CHUNK;
   const int hi = lo + EMB_CHUNK < N ? lo + EMB_CHUNK : N;
+  // the chunk's atomic numbers once per workgroup (every row phase of every column chunk asks for all of them)
+  __shared__ int zs[EMB_CHUNK];
+  for (int i = threadIdx.x; i < EMB_CHUNK; i += 1024) zs[i] = lo + i < hi ? Z[lo + i] : -1;
+  __syncthreads();
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
   for (int i0 = lo + ph; i0 < hi; i0 += 8 * nph) {
     int zz[8];
 #pragma unroll
     for (int u = 0; u < 8; ++u) {
       const int i = i0 + u * nph;
-      zz[u] = i < hi ? Z[i] : -1;
+      zz[u] = i < hi ? zs[i - lo] : -1;
+    }
+    // the rows that match are all asked for before the first one is added (same order of additions)
+    float4 v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (zz[u] == z) v[u] = *reinterpret_cast<const float4*>(g_h + (size_t)(i0 + u * nph) * H + q * 4);
     }
 #pragma unroll
     for (int u = 0; u < 8; ++u) {
-      if (zz[u] == z) {
-        const float4 v = *reinterpret_cast<const float4*>(g_h + (size_t)(i0 + u * nph) * H + q * 4);
-        acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
-      }
+      if (zz[u] == z) { acc.x += v[u].x; acc.y += v[u].y; acc.z += v[u].z; acc.w += v[u].w; }
     }
   }
   sh[threadIdx.x] = acc;
@@ -106,6 +115,47 @@ k_pool_fwd(int H, int mode, const int32_t* __restrict__ graph_off, const float* 
     }
     const float sc = (mode == HGNN_POOL_MEAN && hi > lo) ? 1.0f / (float)(hi - lo) : 1.0f;
     *reinterpret_cast<float4*>(p + (size_t)g * H + q * 4) = make_float4(acc.x * sc, acc.y * sc, acc.z * sc, acc.w * sc);
+  }
+}
+
+// The same pooling for few, large graphs (crystals of thousands of atoms): one workgroup per (graph, 4-column chunk),
+// every thread a row phase with four rows in flight; the phases are added in a fixed order (32 groups of 32).
+__global__ void __launch_bounds__(1024)
+k_pool_fwd_tall(int H, int mode, const int32_t* __restrict__ graph_off, const float* __restrict__ h, float* __restrict__ p) {
+  __shared__ float4 sh[1024];
+  const int g = blockIdx.x, q = blockIdx.y;
+  const int lo = graph_off[g], hi = graph_off[g + 1];
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int i0 = lo + (int)threadIdx.x; i0 < hi; i0 += 4 * 1024) {
+    float4 v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int i = i0 + u * 1024;
+      v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (i < hi) v[u] = *reinterpret_cast<const float4*>(h + (size_t)i * H + q * 4);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) { acc.x += v[u].x; acc.y += v[u].y; acc.z += v[u].z; acc.w += v[u].w; }
+  }
+  sh[threadIdx.x] = acc;
+  __syncthreads();
+  if (threadIdx.x < 32) {
+    float4 s = sh[threadIdx.x * 32];
+    for (int k = 1; k < 32; ++k) {
+      const float4 t = sh[threadIdx.x * 32 + k];
+      s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
+    }
+    sh[threadIdx.x * 32] = s;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float4 s = sh[0];
+    for (int k = 1; k < 32; ++k) {
+      const float4 t = sh[k * 32];
+      s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
+    }
+    const float sc = (mode == HGNN_POOL_MEAN && hi > lo) ? 1.0f / (float)(hi - lo) : 1.0f;
+    *reinterpret_cast<float4*>(p + (size_t)g * H + q * 4) = make_float4(s.x * sc, s.y * sc, s.z * sc, s.w * sc);
   }
 }
 
@@ -535,7 +585,7 @@ static int32_t embed_bwd_launch(hipStream_t st, int32_t N, int32_t H, const int3
   const int nchunk = (N + EMB_CHUNK - 1) / EMB_CHUNK;
   ProfScope ps(PT_EMBED, st);
   if (nchunk > 0) {
-    if (valid_H(H)) k_embed_bwd_part<<<dim3(HGNN_ZMAX + 1, nchunk), 256, 0, st>>>(N, H, Z, g_h, part);
+    if (valid_H(H)) k_embed_bwd_part<<<dim3(HGNN_ZMAX + 1, nchunk), 1024, 0, st>>>(N, H, Z, g_h, part);
     else k_embed_bwd_part_any<<<dim3(HGNN_ZMAX + 1, nchunk), 256, 0, st>>>(N, H, Z, g_h, part);
     HGNN_LAUNCH_CHECK("k_embed_bwd_part");
   }
@@ -602,7 +652,10 @@ extern "C" int32_t hgnn_pool_by_graph_fwd(void* stream, int32_t N, int32_t G, in
   if (G == 0) return HGNN_OK;
   HGNN_REQUIRE(graph_off && p && (h || N == 0), HGNN_ERR_NULLPTR, "pool_fwd: null pointer");
   ProfScope ps(PT_POOL, st);
-  if (valid_H(H)) k_pool_fwd<<<G, 1024, 0, st>>>(H, mode, graph_off, h, p);
+  // few large graphs: a workgroup per graph would leave most of the chip idle (the order of the additions, fixed in
+  // either kernel, depends on which one runs, i.e. on N, G and H only)
+  if (valid_H(H) && (int64_t)N >= 4096 * (int64_t)G) k_pool_fwd_tall<<<dim3(G, H / 4), 1024, 0, st>>>(H, mode, graph_off, h, p);
+  else if (valid_H(H)) k_pool_fwd<<<G, 1024, 0, st>>>(H, mode, graph_off, h, p);
   else k_pool_fwd_any<<<dim3(G, (H + 63) / 64), 256, 0, st>>>(H, mode, graph_off, h, p);
   HGNN_LAUNCH_CHECK("k_pool_fwd");
   return HGNN_OK;

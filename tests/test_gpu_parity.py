@@ -474,6 +474,27 @@ def test_pool_sum_and_mean_overwrite_and_accumulate(H):
         assert relerr(g_h.cpu().numpy(), base.astype(np.float64) + want_g) <= TOL["f32"]["grad"]
 
 
+@pytest.mark.parametrize("H,sizes", [(128, [9000, 4097, 0, 5001]), (64, [12000, 1]), (256, [4096])])
+def test_pool_few_large_graphs(H, sizes):
+    """At 4096 atoms per graph and more the forward pooling splits a graph's columns over workgroups."""
+    say("pool large graphs", H, sizes)
+    import torch
+    from paper_2506_21788_amd import binding as B
+    rng = np.random.default_rng(H + len(sizes))
+    graph_off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    N, G = int(graph_off[-1]), len(sizes)
+    assert N >= 4096 * G
+    h = rng.standard_normal((N, H)).astype(np.float32)
+    for mode, mean in ((B.POOL_SUM, False), (B.POOL_MEAN, True)):
+        p = torch.full((G, H), float("nan"), dtype=torch.float32, device="cuda")
+        B.pool_by_graph_fwd(N, G, H, mode, torch.as_tensor(graph_off).cuda(), torch.as_tensor(h).cuda(), p)
+        want = oracle.pool_fwd(h, graph_off, mean=mean)
+        assert relerr(p.cpu().numpy(), want) <= TOL["f32"]["fwd"]
+        for g, n in enumerate(sizes):
+            if n == 0:
+                assert np.all(p.cpu().numpy()[g] == 0.0)
+
+
 @pytest.mark.parametrize("H,dtype,S", [(256, "bf16", 80), (128, "f32", 300), (64, "f32", 70)])
 def test_step_many_sources(H, dtype, S):
     """More branches than the head weight gradient has compute units per split: most branches see no graph at all."""
