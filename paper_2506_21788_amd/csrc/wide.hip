@@ -355,13 +355,12 @@ __global__ void __launch_bounds__(256, 2) k_fgemm_ad(FGemmArgs p) {
 
   // (the B loads come first: the compiler merges the load counts of this prologue into the loop's own, and fewer
   // loads behind Y here than in the loop would make every iteration wait for nearly all of its loads)
-  u32x4_t aR[4][KC][WI], preX[2], preY[2];
-  {
-    const long k0 = kclamp(0), k1 = kclamp(1);
+  u32x4_t aR[4][KC][WI], pre[4][2];   // pre[k]: the B fragments of the step whose number is k modulo 4
 #pragma unroll
-    for (int s = 0; s < 2; ++s) preX[s] = *reinterpret_cast<const u32x4_t*>(bsrc[s] + k0 * bkst);
+  for (int k = 0; k < 4; ++k) {
+    const long kk0 = kclamp(k);
 #pragma unroll
-    for (int s = 0; s < 2; ++s) preY[s] = *reinterpret_cast<const u32x4_t*>(bsrc[s] + k1 * bkst);
+    for (int s = 0; s < 2; ++s) pre[k][s] = *reinterpret_cast<const u32x4_t*>(bsrc[s] + kk0 * bkst);
   }
 #pragma unroll
   for (int st = 0; st < 3; ++st) {
@@ -372,14 +371,17 @@ __global__ void __launch_bounds__(256, 2) k_fgemm_ad(FGemmArgs p) {
       for (int i = 0; i < WI; ++i) aR[st][kk][i] = *reinterpret_cast<const u32x4_t*>(asrc[i] + (k0 + kk) * akst);
   }
   {
-    const long k2 = kclamp(2);
+    const long k4 = kclamp(4);
 #pragma unroll
-    for (int s = 0; s < 2; ++s) lds[(NW * s + wave) * 64 + lane] = preX[s];
+    for (int s = 0; s < 2; ++s) lds[(NW * s + wave) * 64 + lane] = pre[0][s];
 #pragma unroll
-    for (int s = 0; s < 2; ++s) preX[s] = *reinterpret_cast<const u32x4_t*>(bsrc[s] + k2 * bkst);
+    for (int s = 0; s < 2; ++s) pre[0][s] = *reinterpret_cast<const u32x4_t*>(bsrc[s] + k4 * bkst);
   }
   __syncthreads();
-  // after the prologue: LDS half 0 = B of step 0, Y = B of step 1, X = B of step 2, aR[0..2] = A of steps 0..2
+  // after the prologue: LDS half 0 = B of step 0, pre[1..3] = B of steps 1..3, pre[0] = B of step 4, aR[0..2] = A of
+  // steps 0..2. Loads complete in the order of their issue, so the shortest distance between a load and its use is
+  // what counts: A three steps, B four steps (two with only two register sets: every step then waited for loads
+  // issued two steps earlier).
   for (int c = 0; c < nch; c += 4) {
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
@@ -403,16 +405,13 @@ __global__ void __launch_bounds__(256, 2) k_fgemm_ad(FGemmArgs p) {
 #pragma unroll
         for (int i = 0; i < WI; ++i)
           aR[(r + 3) & 3][kk][i] = *reinterpret_cast<const u32x4_t*>(asrc[i] + (kn + kk) * akst);
-      if (half == 0) {
+      {
+        const long kb5 = kclamp(c + r + 5);
+        u32x4_t* nxt = lds + (half ^ 1) * STAGE;
 #pragma unroll
-        for (int s = 0; s < 2; ++s) lds[STAGE + (NW * s + wave) * 64 + lane] = preY[s];
+        for (int s = 0; s < 2; ++s) nxt[(NW * s + wave) * 64 + lane] = pre[(r + 1) & 3][s];
 #pragma unroll
-        for (int s = 0; s < 2; ++s) preY[s] = *reinterpret_cast<const u32x4_t*>(bsrc[s] + kn * bkst);
-      } else {
-#pragma unroll
-        for (int s = 0; s < 2; ++s) lds[(NW * s + wave) * 64 + lane] = preX[s];
-#pragma unroll
-        for (int s = 0; s < 2; ++s) preX[s] = *reinterpret_cast<const u32x4_t*>(bsrc[s] + kn * bkst);
+        for (int s = 0; s < 2; ++s) pre[(r + 1) & 3][s] = *reinterpret_cast<const u32x4_t*>(bsrc[s] + kb5 * bkst);
       }
       __syncthreads();
     }
