@@ -104,37 +104,74 @@ __device__ __forceinline__ TileRange xcd_tile_range(int ntiles) {
   return {lo + slot, hi, G >> 3};
 }
 
+// The B fragments of the first steps of a tile product, asked for before the workgroup meets at the barrier in front of
+// the product: a wavefront's B stream is a chain of L2 round trips, and with loads issued only where they are used
+// every pair of steps waited for one of them. The fragments come through buffer loads (resource in scalar registers,
+// one per-lane offset register, the fragment's offset in a scalar register), so that no per-fragment 64-bit address
+// lives in vector registers.
+typedef unsigned u32x4_buf_t __attribute__((ext_vector_type(4)));
+template <int H, bool BF16>
+struct BRing {
+  static constexpr int NKB = H / 16;
+  static constexpr int D = BF16 ? (NKB < 4 ? NKB : 4) : 1;   // steps in flight
+  bf16x8_t b[D][ECfg<H, BF16>::CB];
+  __amdgpu_buffer_rsrc_t rsrc;
+  unsigned lo;   // lane offset in bytes
+};
+template <int H, bool BF16>
+__device__ __forceinline__ void tile_b_load(BRing<H, BF16>& ring, int wc, int kb, bf16x8_t (&o)[ECfg<H, BF16>::CB]) {
+  using C = ECfg<H, BF16>;
+#pragma unroll
+  for (int j = 0; j < C::CB; ++j)
+    o[j] = __builtin_bit_cast(bf16x8_t, __builtin_amdgcn_raw_buffer_load_b128(
+                                            ring.rsrc, ring.lo, ((wc * C::CB + j) * (H / 16) + kb) * 1024, 0));
+}
+// Bpacked: the packed H x H block (H * H * 2 bytes)
+template <int H, bool BF16>
+__device__ __forceinline__ void tile_mma_prefetch(const void* Bpacked, int wc, int lane, BRing<H, BF16>& ring) {
+  if constexpr (BF16) {
+    ring.rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(Bpacked), 0, H * H * 2, 0x00020000);
+    ring.lo = lane * 16u;
+    asm volatile("" : "+v"(ring.lo));   // kept as one register: not folded into per-fragment addresses
+#pragma unroll
+    for (int d = 0; d < BRing<H, BF16>::D; ++d) tile_b_load<H, BF16>(ring, wc, d, ring.b[d]);
+  }
+}
+
 // A tile (LDS, row-major, padded) x packed B block -> accumulators; same tiling as the row-tile GEMM.
 // The accumulators start from zero (the first step feeds a constant zero, so they need no clearing).
+// bf16: ring holds the B fragments of the first D steps (tile_mma_prefetch); each step asks for those of step + D.
 template <int H, bool BF16>
 __device__ __forceinline__ void tile_mma(const unsigned char* smem, const void* Bpacked, int wr, int wc, int lane,
-                                         f32x16_t (&acc)[ECfg<H, BF16>::RB][ECfg<H, BF16>::CB]) {
+                                         f32x16_t (&acc)[ECfg<H, BF16>::RB][ECfg<H, BF16>::CB], BRing<H, BF16>& ring) {
   using C = ECfg<H, BF16>;
   const f32x16_t zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   if constexpr (BF16) {
     constexpr int NKB = H / 16;
-    auto step = [&](int kb, auto first) {
-      bf16x8_t a[C::RB];
+    constexpr int D = BRing<H, BF16>::D;
+    // LDS byte offset of this lane's A fragment of the first row block and step (one register; row blocks and steps
+    // are immediate offsets)
+    unsigned ao = (unsigned)(((wr * C::RB * 32 + (lane & 31)) * C::STRIDE + (lane >> 5) * 8) * 2);
+    asm volatile("" : "+v"(ao));
+    bf16x8_t a[2][C::RB];   // A fragments of this step and the next
 #pragma unroll
-      for (int i = 0; i < C::RB; ++i) {
-        const int row = (wr * C::RB + i) * 32 + (lane & 31);
-        a[i] = *reinterpret_cast<const bf16x8_t*>(smem + ((size_t)row * C::STRIDE + kb * 16 + (lane >> 5) * 8) * 2);
-      }
+    for (int i = 0; i < C::RB; ++i) a[0][i] = *reinterpret_cast<const bf16x8_t*>(smem + ao + (i * 32 * C::STRIDE) * 2);
 #pragma unroll
-      for (int j = 0; j < C::CB; ++j) {
-        const bf16x8_t b = ldg_at<bf16x8_t>(uoff(Bpacked, (size_t)((wc * C::CB + j) * NKB + kb) * 1024), lane * 16u);
+    for (int kb = 0; kb < NKB; ++kb) {
+      if (kb + 1 < NKB) {
 #pragma unroll
         for (int i = 0; i < C::RB; ++i)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b, decltype(first)::value ? zero : acc[i][j], 0, 0, 0);
+          a[(kb + 1) & 1][i] = *reinterpret_cast<const bf16x8_t*>(smem + ao + (i * 32 * C::STRIDE + (kb + 1) * 16) * 2);
       }
-    };
-    static_assert(NKB % 4 == 0, "steps are taken four at a time");
-    step(0, std::true_type{});
-    step(1, std::false_type{});
-    step(2, std::false_type{});
-    step(3, std::false_type{});
-#pragma unroll 4
-    for (int kb = 4; kb < NKB; ++kb) step(kb, std::false_type{});
+#pragma unroll
+      for (int j = 0; j < C::CB; ++j)
+#pragma unroll
+        for (int i = 0; i < C::RB; ++i)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kb & 1][i], ring.b[kb % D][j], kb == 0 ? zero : acc[i][j], 0, 0, 0);
+      if (kb + D < NKB) tile_b_load<H, BF16>(ring, wc, kb + D, ring.b[kb % D]);
+      // (without this the scheduler moves every refill down to the step that uses it)
+      __builtin_amdgcn_sched_barrier(0);
+    }
   } else {
     // fp32 operands: the A tile stays fp32 in LDS and is split into three bf16 terms as it is read; B comes as
     // three bf16 planes (launch_pack_x3); six bf16 products per step of 16 k (see split_bf16x3)
@@ -514,6 +551,8 @@ __device__ __forceinline__ void edge_fwd_tile(
       }
     }
   }
+  BRing<H, BF16> ring;
+  if constexpr (!BRES) tile_mma_prefetch<H, BF16>(p.W2p, wc, lane, ring);
   __syncthreads();
   f32x16_t acc[C::RB][C::CB];
 #pragma unroll
@@ -523,7 +562,7 @@ __device__ __forceinline__ void edge_fwd_tile(
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
   if constexpr (BRES) tile_mma_res<H, BF16>(smem, wr, lane, breg, acc);
-  else tile_mma<H, BF16>(smem, p.W2p, wr, wc, lane, acc);
+  else tile_mma<H, BF16>(smem, p.W2p, wr, wc, lane, acc, ring);
   if (tid < 3 * C::TM) s_next[tid] = nxt;
   if constexpr (ATTR) store_attr4(at_next, tid, nxa);
   __syncthreads();
@@ -1251,9 +1290,11 @@ __device__ __forceinline__ void edge_bwd_tile(const EdgeBwdArgs& p, unsigned cha
       for (int j = 0; j < C::CB; ++j) asm volatile("" : "+v"(sb2[j]), "+v"(swx[j]));
     }
   }
+  BRing<H, BF16> ring;
+  tile_mma_prefetch<H, BF16>(p.W2Tp, wc, lane, ring);
   __syncthreads();
   f32x16_t acc[C::RB][C::CB];
-  tile_mma<H, BF16>(smem, p.W2Tp, wr, wc, lane, acc);
+  tile_mma<H, BF16>(smem, p.W2Tp, wr, wc, lane, acc, ring);
   s_next[tid] = nxt;
   if constexpr (ATTR) {
     store_attr4(at_next, tid, nxa);
