@@ -140,15 +140,25 @@ __device__ __forceinline__ void gemm_stage_a(const GemmArgs& p, int kc, int rbeg
     static_assert(ITER % UN == 0, "staging loop must divide evenly");
     for (int it0 = 0; it0 < ITER; it0 += UN) {
       float4 v[UN];
-      // all loads of the batch are issued before any of them is used (rows past the end are clamped, then zeroed)
+      long gr[UN];
+      // all loads of the batch are issued before any of them is used (rows past the end are clamped, then zeroed).
+      // The row indices come first, under one uniform branch: with the test inside the loop every load waited
+      // for the one before it.
+#pragma unroll
+      for (int u = 0; u < UN; ++u) {
+        const int r = (tid + (it0 + u) * 256) / CH;
+        const int pos = rbeg + r;
+        gr[u] = pos < rend ? pos : rend - 1;
+      }
+      if (p.row_idx) {
+#pragma unroll
+        for (int u = 0; u < UN; ++u) gr[u] = p.row_idx[gr[u]];
+      }
 #pragma unroll
       for (int u = 0; u < UN; ++u) {
         const int c = tid + (it0 + u) * 256;
-        const int r = c / CH, q = c - r * CH;
-        int pos = rbeg + r;
-        pos = pos < rend ? pos : rend - 1;
-        const long gr = p.row_idx ? p.row_idx[pos] : pos;
-        v[u] = *reinterpret_cast<const float4*>(A + gr * lda + q * 4);
+        const int q = c % CH;
+        v[u] = *reinterpret_cast<const float4*>(A + gr[u] * lda + q * 4);
       }
 #pragma unroll
       for (int u = 0; u < UN; ++u) {
@@ -176,7 +186,7 @@ template <int H, bool BF16, int TM>
 __device__ __forceinline__ void gemm_multiply(const GemmArgs& p, int kc, int cb, int grp, const unsigned char* smem,
                                               f32x16_t (&acc)[GemmCfg<H, BF16, TM>::RB][GemmCfg<H, BF16, TM>::CB]) {
   using C = GemmCfg<H, BF16, TM>;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: fragment offsets stay in scalar registers
   const int wr = wave / C::WC, wc = wave % C::WC;
   {
     // ---- multiply. All workgroups run this loop at about the same time over the same packed block: each starts at
@@ -184,26 +194,43 @@ __device__ __forceinline__ void gemm_multiply(const GemmArgs& p, int kc, int cb,
     const int krot = blockIdx.x * 5;
     const long bblk0 = grp * p.grp_blk_stride + p.blk[kc][cb];
     if (BF16) {
-      const bf16x8_t* __restrict__ Bp = reinterpret_cast<const bf16x8_t*>(p.B) + bblk0 * (H * H / 8);
+      // B fragments D steps ahead in a register ring, through buffer loads (resource and fragment offset in scalar
+      // registers, one per-lane offset register); A fragments one step ahead. With each load next to its use the
+      // loop was a chain of L2 round trips, one per step. The scheduling barrier keeps the refills where they are.
       constexpr int NKB = H / 16;
-      constexpr int KUN = C::TM > 64 ? 4 : 8;   // operand loads in flight; fewer with the taller tile's accumulators
-#pragma unroll KUN
-      for (int kk = 0; kk < NKB; ++kk) {
+      constexpr int D = NKB < 4 ? NKB : 4;
+      const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
+          const_cast<char*>(reinterpret_cast<const char*>(p.B)) + bblk0 * (long)(H * H * 2), 0, H * H * 2, 0x00020000);
+      unsigned lo = lane * 16u;
+      unsigned ao = (unsigned)(((wr * C::WROWS + (lane & 31)) * C::STRIDE + (lane >> 5) * 8) * 2);
+      asm volatile("" : "+v"(lo), "+v"(ao));   // kept as one register each: not folded into per-step addresses
+      bf16x8_t b[D][C::CB], a[2][C::RB];
+      auto load_b = [&](int kk, bf16x8_t (&o)[C::CB]) {
         const int kb = (kk + krot) & (NKB - 1);
-        bf16x8_t a[C::RB];
 #pragma unroll
-        for (int i = 0; i < C::RB; ++i) {
-          const int row = wr * C::WROWS + i * 32 + (lane & 31);
-          a[i] = *reinterpret_cast<const bf16x8_t*>(smem + ((size_t)row * C::STRIDE + kb * 16 + (lane >> 5) * 8) * 2);
-        }
+        for (int j = 0; j < C::CB; ++j)
+          o[j] = __builtin_bit_cast(bf16x8_t, __builtin_amdgcn_raw_buffer_load_b128(
+                                                  rs, lo, ((wc * C::CB + j) * NKB + kb) * 1024, 0));
+      };
+      auto load_a = [&](int kk, bf16x8_t (&o)[C::RB]) {
+        const int kb = (kk + krot) & (NKB - 1);
 #pragma unroll
-        for (int j = 0; j < C::CB; ++j) {
-          const int nb = wc * C::CB + j;
-          const bf16x8_t b = Bp[(nb * NKB + kb) * 64 + lane];
+        for (int i = 0; i < C::RB; ++i)
+          o[i] = *reinterpret_cast<const bf16x8_t*>(smem + ao + (i * 32 * C::STRIDE + kb * 16) * 2);
+      };
+#pragma unroll
+      for (int d = 0; d < D; ++d) load_b(d, b[d]);
+      load_a(0, a[0]);
+#pragma unroll
+      for (int kk = 0; kk < NKB; ++kk) {
+        if (kk + 1 < NKB) load_a(kk + 1, a[(kk + 1) & 1]);
+#pragma unroll
+        for (int j = 0; j < C::CB; ++j)
 #pragma unroll
           for (int i = 0; i < C::RB; ++i)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b, acc[i][j], 0, 0, 0);
-        }
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kk & 1][i], b[kk % D][j], acc[i][j], 0, 0, 0);
+        if (kk + D < NKB) load_b(kk + D, b[kk % D]);
+        __builtin_amdgcn_sched_barrier(0);
       }
     } else {
       const float4* __restrict__ Bp = reinterpret_cast<const float4*>(p.B) + bblk0 * (H * H / 4);
@@ -300,19 +327,29 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& p, int cb, int grp
       bool ok[NCH];
       float4 mv[NCH], a1[NCH], a2[NCH];
       // every auxiliary load of the pass is issued before any result is stored (rows past the end are clamped)
+      // (each kind of operand under one uniform branch around its loads, not one branch per load)
 #pragma unroll
       for (int k = 0; k < NCH; ++k) {
         const int sr = r0 + k * RSTEP;
-        int pos = rbeg + (sr / 32) * C::WROWS + i * 32 + (sr % 32);
+        const int pos = rbeg + (sr / 32) * C::WROWS + i * 32 + (sr % 32);
         ok[k] = pos < rend;
-        pos = ok[k] ? pos : rend - 1;
-        grow[k] = p.row_idx ? p.row_idx[pos] : pos;
+        grow[k] = ok[k] ? pos : rend - 1;
       }
+      if (p.row_idx) {
 #pragma unroll
-      for (int k = 0; k < NCH; ++k) {
-        if (p.mul) mv[k] = *reinterpret_cast<const float4*>(p.mul + grow[k] * p.ldmul + gcol);
-        if (use_add) a1[k] = *reinterpret_cast<const float4*>(p.add1 + grow[k] * p.ldadd1 + gcol);
-        if (p.add2) a2[k] = *reinterpret_cast<const float4*>(p.add2 + grow[k] * p.ldadd2 + gcol);
+        for (int k = 0; k < NCH; ++k) grow[k] = p.row_idx[grow[k]];
+      }
+      if (p.mul) {
+#pragma unroll
+        for (int k = 0; k < NCH; ++k) mv[k] = *reinterpret_cast<const float4*>(p.mul + grow[k] * p.ldmul + gcol);
+      }
+      if (use_add) {
+#pragma unroll
+        for (int k = 0; k < NCH; ++k) a1[k] = *reinterpret_cast<const float4*>(p.add1 + grow[k] * p.ldadd1 + gcol);
+      }
+      if (p.add2) {
+#pragma unroll
+        for (int k = 0; k < NCH; ++k) a2[k] = *reinterpret_cast<const float4*>(p.add2 + grow[k] * p.ldadd2 + gcol);
       }
 #pragma unroll
       for (int k = 0; k < NCH; ++k) {
