@@ -661,7 +661,7 @@ struct WgradJobs {
 };
 
 template <int H, bool BF16>
-__global__ void __launch_bounds__(256) k_wgrad(WgradJobs m, int nsplit, int rows_per_split, int ny) {
+__global__ void __launch_bounds__(256, 2) k_wgrad(WgradJobs m, int nsplit, int rows_per_split, int ny) {
   using C = WgradCfg<H>;
   __shared__ __align__(16) float sA[WG_RC * C::STRIDE];
   __shared__ __align__(16) float sB[WG_RC * C::STRIDE];
@@ -703,18 +703,25 @@ __global__ void __launch_bounds__(256) k_wgrad(WgradJobs m, int nsplit, int rows
   const int lda = p.lda[ia], ldb = p.ldb[ib];
   constexpr int CH = C::OT / 4;
   constexpr int ITER = WG_RC * CH / 256;   // 1, 2 or 4
-  float4 va[ITER], vb[ITER];
-  // the rows of step r0 (clamped to the last valid row; rows past the end are zeroed when they are staged)
-  auto fetch = [&](long r0) {
+  // the rows of step r0 (clamped to the last valid row; rows past the end are zeroed when they are staged). The
+  // row indices are read first, under one uniform branch: with the test inside the loop every load waited for the
+  // one before it.
+  auto fetch = [&](long r0, float4 (&va)[ITER], float4 (&vb)[ITER]) {
+    long gr[ITER];
 #pragma unroll
     for (int u = 0; u < ITER; ++u) {
-      const int c = tid + u * 256;
-      const int r = c / CH, q = c - r * CH;
-      long pos = r0 + r;
-      pos = pos < rend ? pos : rend - 1;
-      const long gr = p.row_idx ? p.row_idx[pos] : pos;
-      va[u] = *reinterpret_cast<const float4*>(A + gr * lda + ta * C::OT + q * 4);
-      vb[u] = *reinterpret_cast<const float4*>(B + gr * ldb + tb * C::OT + q * 4);
+      const long pos = r0 + (tid + u * 256) / CH;
+      gr[u] = pos < rend ? pos : rend - 1;
+    }
+    if (p.row_idx) {
+#pragma unroll
+      for (int u = 0; u < ITER; ++u) gr[u] = p.row_idx[gr[u]];
+    }
+#pragma unroll
+    for (int u = 0; u < ITER; ++u) {
+      const int q = (tid + u * 256) % CH;
+      va[u] = *reinterpret_cast<const float4*>(A + gr[u] * lda + ta * C::OT + q * 4);
+      vb[u] = *reinterpret_cast<const float4*>(B + gr[u] * ldb + tb * C::OT + q * 4);
     }
   };
   // column sums of this workgroup's B tile ride along where they are asked for (one workgroup per B tile: the
@@ -722,8 +729,9 @@ __global__ void __launch_bounds__(256) k_wgrad(WgradJobs m, int nsplit, int rows
   const bool do_cs = m.colsum_partial != nullptr && (p.colsum_dest[0] || p.colsum_dest[1]) && ia == 0 && ta == 0;
   static_assert(256 % CH == 0, "a thread keeps its chunk column over the steps");
   float4 cs = make_float4(0.f, 0.f, 0.f, 0.f);
-  if (rbeg < rend) fetch(rbeg);
-  for (long r0 = rbeg; r0 < rend; r0 += WG_RC) {
+  // one step: the rows held in va / vb go to LDS, the registers are refilled with the rows two steps on (they travel
+  // while this step and the next are multiplied), then the product
+  auto step = [&](long r0, float4 (&va)[ITER], float4 (&vb)[ITER]) {
     __syncthreads();
 #pragma unroll
     for (int u = 0; u < ITER; ++u) {
@@ -736,8 +744,7 @@ __global__ void __launch_bounds__(256) k_wgrad(WgradJobs m, int nsplit, int rows
       *reinterpret_cast<float4*>(&sA[r * C::STRIDE + q * 4]) = a;
       *reinterpret_cast<float4*>(&sB[r * C::STRIDE + q * 4]) = b;
     }
-    // the next step's rows travel while this step is multiplied
-    if (r0 + WG_RC < rend) fetch(r0 + WG_RC);
+    if (r0 + 2 * WG_RC < rend) fetch(r0 + 2 * WG_RC, va, vb);
     __syncthreads();
     if (BF16) {
 #pragma unroll
@@ -782,6 +789,13 @@ __global__ void __launch_bounds__(256) k_wgrad(WgradJobs m, int nsplit, int rows
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
       }
     }
+  };
+  float4 va0[ITER], vb0[ITER], va1[ITER], vb1[ITER];
+  if (rbeg < rend) fetch(rbeg, va0, vb0);
+  if (rbeg + WG_RC < rend) fetch(rbeg + WG_RC, va1, vb1);
+  for (long r0 = rbeg; r0 < rend; r0 += 2 * WG_RC) {
+    step(r0, va0, vb0);
+    if (r0 + WG_RC < rend) step(r0 + WG_RC, va1, vb1);
   }
   if (do_cs) {   // uniform over the workgroup: row phases are added in order through LDS
     __syncthreads();
