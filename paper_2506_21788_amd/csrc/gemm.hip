@@ -872,12 +872,16 @@ static int32_t launch_wgrad_t(hipStream_t st, const WgradArgs* jobs, int njobs) 
   const int nblk = m.blk_off[njobs];
   const int groups = a.grp_ptr ? a.S : 1;
   const int ny = m.ny_off[njobs];
-  // Splits: never more than the workspace was sized for; at most one round of resident workgroups (a second,
-  // partly filled round costs a whole one); and below that a whole number of workgroups per CU, so that no CU
-  // carries two while its neighbour carries one. Fewer splits also mean fewer partials to write and add up.
+  // Splits: never more than the workspace was sized for, and at most one round of resident workgroups (a second,
+  // partly filled round costs a whole one). Split s runs on XCD s % 8, so the round is counted per XCD: a whole
+  // number of splits on each of them (25 splits of 20 workgroups put 80 workgroups on the first XCD's 64 places
+  // and doubled the kernel's time). Below one round: a whole number of workgroups per CU, so that no CU carries two
+  // while its neighbour carries one. Fewer splits also mean fewer partials to write and add up.
   int nsplit = wgrad_splits(a.M);
   const long per_split = (long)ny * groups;
-  const long one_round = (long)wgrad_resident_wgs<H, BF16>() * num_cus() / per_split;
+  const long xcd_places = (long)wgrad_resident_wgs<H, BF16>() * (num_cus() / 8);
+  const long one_round = xcd_places / per_split >= 1 ? 8 * (xcd_places / per_split)
+                                                     : (long)wgrad_resident_wgs<H, BF16>() * num_cus() / per_split;
   if (nsplit > one_round) {
     nsplit = one_round < 1 ? 1 : (int)one_round;
   } else {
