@@ -113,29 +113,31 @@ typedef unsigned u32x4_buf_t __attribute__((ext_vector_type(4)));
 template <int H, bool BF16>
 struct BRing {
   static constexpr int NKB = H / 16;
-  static constexpr int D = BF16 ? (NKB < 4 ? NKB : 4) : 1;   // steps in flight
-  bf16x8_t b[D][ECfg<H, BF16>::CB];
+  static constexpr int D = BF16 ? (NKB < 4 ? NKB : 4) : 2;   // steps in flight
+  static constexpr int P = BF16 ? 1 : 3;                      // planes of B (fp32 operands: three bf16 terms)
+  bf16x8_t b[D][ECfg<H, BF16>::CB][P];
   __amdgpu_buffer_rsrc_t rsrc;
   unsigned lo;   // lane offset in bytes
 };
 template <int H, bool BF16>
-__device__ __forceinline__ void tile_b_load(BRing<H, BF16>& ring, int wc, int kb, bf16x8_t (&o)[ECfg<H, BF16>::CB]) {
+__device__ __forceinline__ void tile_b_load(BRing<H, BF16>& ring, int wc, int kb,
+                                            bf16x8_t (&o)[ECfg<H, BF16>::CB][BRing<H, BF16>::P]) {
   using C = ECfg<H, BF16>;
 #pragma unroll
   for (int j = 0; j < C::CB; ++j)
-    o[j] = __builtin_bit_cast(bf16x8_t, __builtin_amdgcn_raw_buffer_load_b128(
-                                            ring.rsrc, ring.lo, ((wc * C::CB + j) * (H / 16) + kb) * 1024, 0));
+#pragma unroll
+    for (int q = 0; q < BRing<H, BF16>::P; ++q)
+      o[j][q] = __builtin_bit_cast(bf16x8_t, __builtin_amdgcn_raw_buffer_load_b128(
+                                                 ring.rsrc, ring.lo, q * (H * H * 2) + ((wc * C::CB + j) * (H / 16) + kb) * 1024, 0));
 }
-// Bpacked: the packed H x H block (H * H * 2 bytes)
+// Bpacked: the packed H x H block (bf16: H * H * 2 bytes; fp32 operands: three such planes)
 template <int H, bool BF16>
 __device__ __forceinline__ void tile_mma_prefetch(const void* Bpacked, int wc, int lane, BRing<H, BF16>& ring) {
-  if constexpr (BF16) {
-    ring.rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(Bpacked), 0, H * H * 2, 0x00020000);
-    ring.lo = lane * 16u;
-    asm volatile("" : "+v"(ring.lo));   // kept as one register: not folded into per-fragment addresses
+  ring.rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(Bpacked), 0, BRing<H, BF16>::P * H * H * 2, 0x00020000);
+  ring.lo = lane * 16u;
+  asm volatile("" : "+v"(ring.lo));   // kept as one register: not folded into per-fragment addresses
 #pragma unroll
-    for (int d = 0; d < BRing<H, BF16>::D; ++d) tile_b_load<H, BF16>(ring, wc, d, ring.b[d]);
-  }
+  for (int d = 0; d < BRing<H, BF16>::D; ++d) tile_b_load<H, BF16>(ring, wc, d, ring.b[d]);
 }
 
 // A tile (LDS, row-major, padded) x packed B block -> accumulators; same tiling as the row-tile GEMM.
@@ -167,7 +169,7 @@ __device__ __forceinline__ void tile_mma(const unsigned char* smem, const void* 
       for (int j = 0; j < C::CB; ++j)
 #pragma unroll
         for (int i = 0; i < C::RB; ++i)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kb & 1][i], ring.b[kb % D][j], kb == 0 ? zero : acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kb & 1][i], ring.b[kb % D][j][0], kb == 0 ? zero : acc[i][j], 0, 0, 0);
       if (kb + D < NKB) tile_b_load<H, BF16>(ring, wc, kb + D, ring.b[kb % D]);
       // (without this the scheduler moves every refill down to the step that uses it)
       __builtin_amdgcn_sched_barrier(0);
@@ -176,34 +178,26 @@ __device__ __forceinline__ void tile_mma(const unsigned char* smem, const void* 
     // fp32 operands: the A tile stays fp32 in LDS and is split into three bf16 terms as it is read; B comes as
     // three bf16 planes (launch_pack_x3); six bf16 products per step of 16 k (see split_bf16x3)
     constexpr int NKB = H / 16;
-    constexpr size_t PLANE = (size_t)H * H * 2;
-    auto step = [&](int kb, auto first) {
+    constexpr int D = BRing<H, BF16>::D;
+    unsigned ao = (unsigned)(((wr * C::RB * 32 + (lane & 31)) * C::STRIDE + (lane >> 5) * 8) * 4);
+    asm volatile("" : "+v"(ao));
+#pragma unroll
+    for (int kb = 0; kb < NKB; ++kb) {
       bf16x8_t a[C::RB][3];
 #pragma unroll
       for (int i = 0; i < C::RB; ++i) {
-        const int row = (wr * C::RB + i) * 32 + (lane & 31);
-        const float* ap = reinterpret_cast<const float*>(smem) + (size_t)row * C::STRIDE + kb * 16 + (lane >> 5) * 8;
-        const float4 lo = *reinterpret_cast<const float4*>(ap), hi = *reinterpret_cast<const float4*>(ap + 4);
+        const unsigned char* ap = smem + ao + (i * 32 * C::STRIDE + kb * 16) * 4;
+        const float4 lo = *reinterpret_cast<const float4*>(ap), hi = *reinterpret_cast<const float4*>(ap + 16);
         const float x[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
         split_bf16x3(x, a[i]);
       }
 #pragma unroll
-      for (int j = 0; j < C::CB; ++j) {
-        bf16x8_t b[3];
+      for (int j = 0; j < C::CB; ++j)
 #pragma unroll
-        for (int q = 0; q < 3; ++q)
-          b[q] = ldg_at<bf16x8_t>(uoff(Bpacked, q * PLANE + (size_t)((wc * C::CB + j) * NKB + kb) * 1024), lane * 16u);
-#pragma unroll
-        for (int i = 0; i < C::RB; ++i) acc[i][j] = mfma_bf16x3(a[i], b, decltype(first)::value ? zero : acc[i][j]);
-      }
-    };
-    static_assert(NKB % 4 == 0, "steps are taken four at a time");
-    step(0, std::true_type{});
-    step(1, std::false_type{});
-    step(2, std::false_type{});
-    step(3, std::false_type{});
-#pragma unroll 4
-    for (int kb = 4; kb < NKB; ++kb) step(kb, std::false_type{});
+        for (int i = 0; i < C::RB; ++i) acc[i][j] = mfma_bf16x3(a[i], ring.b[kb % D][j], kb == 0 ? zero : acc[i][j]);
+      if (kb + D < NKB) tile_b_load<H, BF16>(ring, wc, kb + D, ring.b[kb % D]);
+      __builtin_amdgcn_sched_barrier(0);
+    }
   }
 }
 
