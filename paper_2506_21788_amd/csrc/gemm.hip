@@ -952,15 +952,28 @@ __global__ void __launch_bounds__(256) k_colsum(ColsumArgs p, int H, int nsplit,
   for (long r0 = rbeg + ph; r0 < rend; r0 += 4 * nph) {
     float4 xv[4];
     float wv[4];
+    long gr[4];
+    // (indices, rows and weights each under one uniform branch: with the tests inside the loop the loads wait for
+    // one another)
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
-      long r = r0 + (long)u * nph;
-      r = r < rend ? r : rend - 1;
-      const long gr = p.row_idx ? p.row_idx[r] : r;
-      xv[u] = *reinterpret_cast<const float4*>(p.X + gr * p.ldx + q * 4);
-      wv[u] = p.w ? p.w[gr] : 1.f;
-      if (r0 + (long)u * nph >= rend) wv[u] = 0.f;
+      const long r = r0 + (long)u * nph;
+      gr[u] = r < rend ? r : rend - 1;
+      wv[u] = 1.f;
     }
+    if (p.row_idx) {
+#pragma unroll
+      for (int u = 0; u < 4; ++u) gr[u] = p.row_idx[gr[u]];
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) xv[u] = *reinterpret_cast<const float4*>(p.X + gr[u] * p.ldx + q * 4);
+    if (p.w) {
+#pragma unroll
+      for (int u = 0; u < 4; ++u) wv[u] = p.w[gr[u]];
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+      if (r0 + (long)u * nph >= rend) wv[u] = 0.f;
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       float4 x = xv[u];
@@ -980,7 +993,7 @@ __global__ void __launch_bounds__(256) k_colsum(ColsumArgs p, int H, int nsplit,
 }
 
 static int colsum_splits(int64_t M) {
-  int64_t s = (M + 255) / 256;
+  int64_t s = (M + 63) / 64;   // 64 rows per workgroup: four trips of loads each (at 256 rows a workgroup's chain of trips set the kernel's time)
   if (s < 1) s = 1;
   if (s > 1024) s = 1024;
   return (int)s;
