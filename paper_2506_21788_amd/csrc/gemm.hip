@@ -233,29 +233,47 @@ __device__ __forceinline__ void gemm_multiply(const GemmArgs& p, int kc, int cb,
         __builtin_amdgcn_sched_barrier(0);
       }
     } else {
-      const float4* __restrict__ Bp = reinterpret_cast<const float4*>(p.B) + bblk0 * (H * H / 4);
+      // the same ring for fp32 operands (four steps of 8 k ahead; A fragments one step ahead)
       constexpr int NKB = H / 8;
-#pragma unroll 4
-      for (int kk = 0; kk < NKB; ++kk) {
+      constexpr int D = 4;
+      const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
+          const_cast<char*>(reinterpret_cast<const char*>(p.B)) + bblk0 * (long)(H * H * 4), 0, H * H * 4, 0x00020000);
+      unsigned lo = lane * 16u;
+      unsigned ao = (unsigned)(((wr * C::WROWS + (lane & 31)) * C::STRIDE + (lane >> 5) * 4) * 4);
+      asm volatile("" : "+v"(lo), "+v"(ao));
+      typedef float f32x4v_t __attribute__((ext_vector_type(4)));
+      f32x4v_t b[D][C::CB], a[2][C::RB];
+      auto load_b = [&](int kk, f32x4v_t (&o)[C::CB]) {
         const int kb = (kk + krot) & (NKB - 1);
-        float4 a[C::RB];
 #pragma unroll
-        for (int i = 0; i < C::RB; ++i) {
-          const int row = wr * C::WROWS + i * 32 + (lane & 31);
-          a[i] = *reinterpret_cast<const float4*>(smem + ((size_t)row * C::STRIDE + kb * 8 + (lane >> 5) * 4) * 4);
-        }
+        for (int j = 0; j < C::CB; ++j)
+          o[j] = __builtin_bit_cast(f32x4v_t, __builtin_amdgcn_raw_buffer_load_b128(
+                                                  rs, lo, ((wc * C::CB + j) * NKB + kb) * 1024, 0));
+      };
+      auto load_a = [&](int kk, f32x4v_t (&o)[C::RB]) {
+        const int kb = (kk + krot) & (NKB - 1);
 #pragma unroll
-        for (int j = 0; j < C::CB; ++j) {
-          const int nb = wc * C::CB + j;
-          const float4 b = Bp[(nb * NKB + kb) * 64 + lane];
+        for (int i = 0; i < C::RB; ++i)
+          o[i] = *reinterpret_cast<const f32x4v_t*>(smem + ao + (i * 32 * C::STRIDE + kb * 8) * 4);
+      };
+#pragma unroll
+      for (int d = 0; d < D; ++d) load_b(d, b[d]);
+      load_a(0, a[0]);
+#pragma unroll
+      for (int kk = 0; kk < NKB; ++kk) {
+        if (kk + 1 < NKB) load_a(kk + 1, a[(kk + 1) & 1]);
+#pragma unroll
+        for (int j = 0; j < C::CB; ++j)
 #pragma unroll
           for (int i = 0; i < C::RB; ++i) {
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].x, b.x, acc[i][j], 0, 0, 0);
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].y, b.y, acc[i][j], 0, 0, 0);
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].z, b.z, acc[i][j], 0, 0, 0);
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i].w, b.w, acc[i][j], 0, 0, 0);
+            const f32x4v_t av = a[kk & 1][i], bv = b[kk % D][j];
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av.x, bv.x, acc[i][j], 0, 0, 0);
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av.y, bv.y, acc[i][j], 0, 0, 0);
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av.z, bv.z, acc[i][j], 0, 0, 0);
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av.w, bv.w, acc[i][j], 0, 0, 0);
           }
-        }
+        if (kk + D < NKB) load_b(kk + D, b[kk % D]);
+        __builtin_amdgcn_sched_barrier(0);
       }
     }
   }
