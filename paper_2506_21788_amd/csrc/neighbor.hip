@@ -400,6 +400,7 @@ struct SearchLds {
   __align__(16) unsigned long long row[4][SR_CAP + 4];   // per wavefront: (atom << 24 | code) of the hits of one row
   float cx[SR_CHUNK], cy[SR_CHUNK], cz[SR_CHUNK];   // shifted candidate positions  pos_j + t
   int cj[SR_CHUNK], cc[SR_CHUNK];                   // candidate atom and shift code
+  int ch[SR_CHUNK];                                 // counting pass: hits of each staged candidate in this work item
   int ext_start[SR_EXT];                            // first record of each enumerated bin
   int ext_pref[SR_EXT + 1];                         // exclusive prefix of their atom counts
   int ext_code[SR_EXT];
@@ -548,7 +549,9 @@ __global__ void __launch_bounds__(256) k_search(SearchArgs p) {
       }
     };
     // this wavefront's destination atom against the n staged candidates; cnt = hits so far
-    auto scan = [&](int i, float pix, float piy, float piz, int n, int& cnt) {
+    // lds_hist (counting pass): a hit adds to the candidate's LDS counter (flushed by the caller) instead of to the
+    // source histogram in memory
+    auto scan = [&](int i, float pix, float piy, float piz, int n, int& cnt, bool lds_hist) {
       for (int k0 = 0; k0 < n; k0 += 256) {
         // four groups of 64 candidates: their LDS reads are in flight together
         int jj[4], cd[4];
@@ -572,6 +575,8 @@ __global__ void __launch_bounds__(256) k_search(SearchArgs p) {
             if (FILL) {
               const int at = cnt + __popcll(mask & ((1ull << lane) - 1ull));
               if (at < SR_CAP) row[at] = ((unsigned long long)(unsigned)jj[u] << 24) | (unsigned)cd[u];
+            } else if (lds_hist) {
+              atomicAdd(&L.ch[k], 1);
             } else {
               atomicAdd(&p.colT_cnt[jj[u]], 1);
             }
@@ -630,6 +635,9 @@ __global__ void __launch_bounds__(256) k_search(SearchArgs p) {
     if (next <= SR_EXT && total0 <= SR_CHUNK) {
       // the usual case: every candidate fits in LDS at once; staged once, then the wavefronts run on their own
       stage(0, total0);
+      if (!FILL) {
+        for (int k = tid; k < total0; k += 256) L.ch[k] = 0;
+      }
       __syncthreads();
       for (int r = 0; r < nrounds; ++r) {
         const int h = 4 * r + wave;
@@ -637,8 +645,17 @@ __global__ void __launch_bounds__(256) k_search(SearchArgs p) {
         const float4 a = p.spos[hb_start + h0 + h];
         const int i = __float_as_int(a.w);
         int cnt = 0;
-        scan(i, a.x, a.y, a.z, total0, cnt);
+        scan(i, a.x, a.y, a.z, total0, cnt, true);
         finish(i, a.x, a.y, a.z, cnt);
+      }
+      if (!FILL) {
+        // the source histogram: one addition per candidate that was hit (a candidate is hit by up to 16 destination
+        // atoms of the work item), not one per hit
+        __syncthreads();
+        for (int k = tid; k < total0; k += 256) {
+          const int c = L.ch[k];
+          if (c) atomicAdd(&p.colT_cnt[L.cj[k]], c);
+        }
       }
     } else {
       // many periodic images or a crowded bin: the candidates are streamed through LDS in chunks, once per round
@@ -656,7 +673,7 @@ __global__ void __launch_bounds__(256) k_search(SearchArgs p) {
             __syncthreads();               // the previous chunk has been read by every wavefront
             stage(c0, n);
             __syncthreads();
-            if (on) scan(i, a.x, a.y, a.z, n, cnt);
+            if (on) scan(i, a.x, a.y, a.z, n, cnt, false);
           }
           __syncthreads();                 // before the bin table is overwritten
         }
