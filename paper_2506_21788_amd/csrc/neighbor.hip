@@ -400,7 +400,11 @@ struct SearchLds {
   __align__(16) unsigned long long row[4][SR_CAP + 4];   // per wavefront: (atom << 24 | code) of the hits of one row
   float cx[SR_CHUNK], cy[SR_CHUNK], cz[SR_CHUNK];   // shifted candidate positions  pos_j + t
   int cj[SR_CHUNK], cc[SR_CHUNK];                   // candidate atom and shift code
-  int ch[SR_CHUNK];                                 // counting pass: hits of each staged candidate in this work item
+  int ch[SR_CHUNK];                                 // hits of each staged candidate in this work item (then, in the
+                                                    // filling pass: the candidate's first place in its source group)
+  unsigned short rowk[4][SR_CAP];                   // per wavefront: candidate slot of each hit of the row at hand
+  unsigned short rinfo[SR_HOME][SR_CAP];            // per destination atom and edge: slot | place among the item's hits << 10
+  int rstart[SR_HOME], rcnt[SR_HOME];               // first edge and edge count of the item's rows (0: row not dealt here)
   int ext_start[SR_EXT];                            // first record of each enumerated bin
   int ext_pref[SR_EXT + 1];                         // exclusive prefix of their atom counts
   int ext_code[SR_EXT];
@@ -429,6 +433,9 @@ struct SearchArgs {
   int8_t* shift;
   float* d2;
   float* rvec;
+  const int32_t* colT_ptr;   // fill: first place of each source's group
+  int32_t* colT_cur;         // fill: places of each group handed out so far
+  int32_t* unsorted;         // fill: the groups' edges in the order they were dealt
   int32_t* novf;       // number of rows left to the slow path
   int32_t* ovf_rows;   // those rows
 };
@@ -574,7 +581,10 @@ __global__ void __launch_bounds__(256) k_search(SearchArgs p) {
           if (hit) {
             if (FILL) {
               const int at = cnt + __popcll(mask & ((1ull << lane) - 1ull));
-              if (at < SR_CAP) row[at] = ((unsigned long long)(unsigned)jj[u] << 24) | (unsigned)cd[u];
+              if (at < SR_CAP) {
+                row[at] = ((unsigned long long)(unsigned)jj[u] << 24) | (unsigned)cd[u];
+                L.rowk[wave][at] = (unsigned short)k;
+              }
             } else if (lds_hist) {
               atomicAdd(&L.ch[k], 1);
             } else {
@@ -586,19 +596,26 @@ __global__ void __launch_bounds__(256) k_search(SearchArgs p) {
       }
     };
     // the row is complete: count, or order it and write the edges
-    auto finish = [&](int i, float pix, float piy, float piz, int cnt) {
+    // h >= 0: the row's edges are dealt to their sources at the end of the work item (slot and place kept in LDS);
+    // h < 0 (candidates streamed in chunks): every edge takes its place with an addition of its own
+    auto finish = [&](int i, float pix, float piy, float piz, int cnt, int h) {
       if (!FILL) {
         if (lane == 0) p.deg[i] = cnt;
         return;
       }
       if (cnt > SR_CAP) {
         if (lane == 0) p.ovf_rows[atomicAdd(p.novf, 1)] = i;
+        if (h >= 0 && lane == 0) L.rcnt[h] = 0;
         return;
       }
       if (lane < 3) row[cnt + lane] = ~0ull;   // pad to a multiple of four for the 16-byte reads below
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
       __builtin_amdgcn_wave_barrier();
       const int start = p.row_ptr[i];
+      if (h >= 0 && lane == 0) {
+        L.rstart[h] = start;
+        L.rcnt[h] = cnt;
+      }
       for (int t = lane; t < cnt; t += 64) {
         const unsigned long long key = row[t];
         int rank = 0;
@@ -617,6 +634,13 @@ __global__ void __launch_bounds__(256) k_search(SearchArgs p) {
         const float qz = __fadd_rn(p.pos[3 * (size_t)mj + 2], tz);
         const float rx = __fsub_rn(pix, qx), ry = __fsub_rn(piy, qy), rz = __fsub_rn(piz, qz);
         const float dd = __fadd_rn(__fadd_rn(__fmul_rn(rx, rx), __fmul_rn(ry, ry)), __fmul_rn(rz, rz));
+        if (h >= 0) {
+          const int k = L.rowk[wave][t];
+          const int place = atomicAdd(&L.ch[k], 1);   // < SR_HOME: a destination atom hits a slot once
+          L.rinfo[h][rank] = (unsigned short)(k | (place << 10));
+        } else {
+          p.unsorted[p.colT_ptr[mj] + atomicAdd(&p.colT_cur[mj], 1)] = e;
+        }
         p.dst[e] = i;
         p.col[e] = mj;
         p.shift[3 * (size_t)e] = (int8_t)s0;
@@ -635,9 +659,7 @@ __global__ void __launch_bounds__(256) k_search(SearchArgs p) {
     if (next <= SR_EXT && total0 <= SR_CHUNK) {
       // the usual case: every candidate fits in LDS at once; staged once, then the wavefronts run on their own
       stage(0, total0);
-      if (!FILL) {
-        for (int k = tid; k < total0; k += 256) L.ch[k] = 0;
-      }
+      for (int k = tid; k < total0; k += 256) L.ch[k] = 0;
       __syncthreads();
       for (int r = 0; r < nrounds; ++r) {
         const int h = 4 * r + wave;
@@ -646,7 +668,7 @@ __global__ void __launch_bounds__(256) k_search(SearchArgs p) {
         const int i = __float_as_int(a.w);
         int cnt = 0;
         scan(i, a.x, a.y, a.z, total0, cnt, true);
-        finish(i, a.x, a.y, a.z, cnt);
+        finish(i, a.x, a.y, a.z, cnt, h);
       }
       if (!FILL) {
         // the source histogram: one addition per candidate that was hit (a candidate is hit by up to 16 destination
@@ -655,6 +677,23 @@ __global__ void __launch_bounds__(256) k_search(SearchArgs p) {
         for (int k = tid; k < total0; k += 256) {
           const int c = L.ch[k];
           if (c) atomicAdd(&p.colT_cnt[L.cj[k]], c);
+        }
+      } else {
+        // transpose plan: every candidate that was hit takes its places in its source group with one addition, then
+        // the item's edges go to their places (any order inside a group: the groups are put in edge order afterwards)
+        __syncthreads();
+        for (int k = tid; k < total0; k += 256) {
+          const int c = L.ch[k];
+          if (c) L.ch[k] = atomicAdd(&p.colT_cur[L.cj[k]], c);
+        }
+        __syncthreads();
+        for (int h = wave; h < nhome; h += 4) {
+          const int cnt = L.rcnt[h], start = L.rstart[h];
+          for (int t = lane; t < cnt; t += 64) {
+            const int info = L.rinfo[h][t];
+            const int k = info & 1023;
+            p.unsorted[p.colT_ptr[L.cj[k]] + L.ch[k] + (info >> 10)] = start + t;
+          }
         }
       }
     } else {
@@ -677,7 +716,7 @@ __global__ void __launch_bounds__(256) k_search(SearchArgs p) {
           }
           __syncthreads();                 // before the bin table is overwritten
         }
-        if (on) finish(i, a.x, a.y, a.z, cnt);
+        if (on) finish(i, a.x, a.y, a.z, cnt, -1);
       }
     }
     __syncthreads();                       // before the next work item reuses the tables
@@ -756,7 +795,8 @@ k_long_rows_emit(const int32_t* __restrict__ novf, const int32_t* __restrict__ o
                  const GMeta* __restrict__ meta, const int32_t* __restrict__ atom_graph,
                  const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ key_j,
                  const int32_t* __restrict__ key_c, int32_t* __restrict__ dst, int32_t* __restrict__ col,
-                 int8_t* __restrict__ shift, float* __restrict__ d2, float* __restrict__ rvec) {
+                 int8_t* __restrict__ shift, float* __restrict__ d2, float* __restrict__ rvec,
+                 const int32_t* __restrict__ colT_ptr, int32_t* __restrict__ colT_cur, int32_t* __restrict__ unsorted) {
   const int w0 = (int)(((size_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6);
   const int nw = (int)(((size_t)gridDim.x * blockDim.x) >> 6);
   const int lane = threadIdx.x & 63;
@@ -782,6 +822,7 @@ k_long_rows_emit(const int32_t* __restrict__ novf, const int32_t* __restrict__ o
       const float qz = __fadd_rn(pos[3 * (size_t)mj + 2], tz);
       const float rx = __fsub_rn(pix, qx), ry = __fsub_rn(piy, qy), rz = __fsub_rn(piz, qz);
       const float dd = __fadd_rn(__fadd_rn(__fmul_rn(rx, rx), __fmul_rn(ry, ry)), __fmul_rn(rz, rz));
+      unsorted[colT_ptr[mj] + atomicAdd(&colT_cur[mj], 1)] = e;   // the edge's place in its source group
       dst[e] = i;
       col[e] = mj;
       shift[3 * (size_t)e] = (int8_t)s0;
@@ -802,22 +843,14 @@ __global__ void k_edge_graph_ptr(int G, const int32_t* __restrict__ graph_off, c
 }
 
 // ---------------------------------------------------------------------------------------------
-// transpose plan: the histogram of sources is taken by the counting search; here the edges are dealt to their
-// source's group through a cursor (any order) and each group is then put into ascending edge order
+// transpose plan: the histogram of sources is taken by the counting search; the filling search deals the edges to
+// their source's group (any order, see k_search); here each group is put into ascending edge order, in place
 // ---------------------------------------------------------------------------------------------
-__global__ void k_fill_sources(int64_t E, const int32_t* __restrict__ col, const int32_t* __restrict__ colT_ptr,
-                               int32_t* __restrict__ cur, int32_t* __restrict__ unsorted) {
-  int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (e >= E) return;
-  int j = col[e];
-  int k = atomicAdd(&cur[j], 1);
-  unsorted[colT_ptr[j] + k] = (int32_t)e;
-}
-
 constexpr int TS_CAP = 512;   // group members ranked out of LDS; longer groups are ranked from memory
 __global__ void __launch_bounds__(256)
-k_rank_sources(int N, const int32_t* __restrict__ colT_ptr, const int32_t* __restrict__ unsorted,
-               int32_t* __restrict__ permT) {
+k_rank_sources(int N, const int32_t* __restrict__ colT_ptr, int32_t* __restrict__ permT, int32_t* __restrict__ copy) {
+  // permT holds the groups as they were dealt; copy: room for one int per edge (long groups are ranked out of it)
+  const int32_t* unsorted = permT;
   __shared__ __align__(16) int grp[4][TS_CAP + 4];
   const int j = (int)(((size_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6);
   const int lane = threadIdx.x & 63;
@@ -842,10 +875,13 @@ k_rank_sources(int N, const int32_t* __restrict__ colT_ptr, const int32_t* __res
     }
     return;
   }
+  for (int t = start + lane; t < end; t += 64) copy[t] = unsorted[t];
+  __threadfence();
+  __builtin_amdgcn_wave_barrier();
   for (int t = start + lane; t < end; t += 64) {
-    const int me = unsorted[t];
+    const int me = copy[t];
     int rank = 0;
-    for (int u = start; u < end; ++u) rank += unsorted[u] < me;
+    for (int u = start; u < end; ++u) rank += copy[u] < me;
     permT[start + rank] = me;
   }
 }
@@ -1045,6 +1081,7 @@ extern "C" int32_t hgnn_radius_graph_fill(void* stream, int32_t N, int32_t G, co
       ProfScope ps(PT_NEIGH_FILL, st);
       SearchArgs a = search_args(w, N, pos, rc);
       a.row_ptr = row_ptr; a.dst = dst; a.col = col; a.shift = shift; a.d2 = d2; a.rvec = rvec;
+      a.colT_ptr = w.colT_ptr; a.colT_cur = w.colT_cur; a.unsorted = permT;   // the groups are ordered in place below
       k_search<true><<<SR_GRID < N ? SR_GRID : N, 256, 0, st>>>(a);
       HGNN_LAUNCH_CHECK("k_search<fill>");
     }
@@ -1055,7 +1092,7 @@ extern "C" int32_t hgnn_radius_graph_fill(void* stream, int32_t N, int32_t G, co
                                             w.bin_atoms, rc, row_ptr, key_j, key_c);
     HGNN_LAUNCH_CHECK("k_long_rows_hits");
     k_long_rows_emit<<<lgrid, 256, 0, st>>>(w.status + 2, w.ovf_rows, pos, w.meta, w.atom_graph, row_ptr, key_j, key_c,
-                                            dst, col, shift, d2, rvec);
+                                            dst, col, shift, d2, rvec, w.colT_ptr, w.colT_cur, permT);
     HGNN_LAUNCH_CHECK("k_long_rows_emit");
   }
   ProfScope pst(PT_NEIGH_TRANSPOSE, st);
@@ -1064,10 +1101,7 @@ extern "C" int32_t hgnn_radius_graph_fill(void* stream, int32_t N, int32_t G, co
   k_copy_i32<<<nblk((int64_t)N + 1, 256), 256, 0, st>>>(w.colT_ptr, colT_ptr, (int64_t)N + 1);
   HGNN_LAUNCH_CHECK("k_copy_i32");
   if (E > 0) {
-    int32_t* unsorted = key_j;  // the keys are dead by now
-    k_fill_sources<<<nblk(E, 256), 256, 0, st>>>(E, col, colT_ptr, w.colT_cur, unsorted);
-    HGNN_LAUNCH_CHECK("k_fill_sources");
-    k_rank_sources<<<nblk((int64_t)N * 64, 256), 256, 0, st>>>(N, colT_ptr, unsorted, permT);
+    k_rank_sources<<<nblk((int64_t)N * 64, 256), 256, 0, st>>>(N, colT_ptr, permT, key_j);   // the keys are dead by now
     HGNN_LAUNCH_CHECK("k_rank_sources");
   }
   return HGNN_OK;
