@@ -581,9 +581,9 @@ struct ReduceArgs {
   long grp_dest_stride;
 };
 
-__global__ void __launch_bounds__(256) k_reduce_partials(ReduceArgs a) {
-  const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
-  const int blk = blockIdx.y, grp = blockIdx.z;
+// wide blocks: one thread per element
+__device__ __forceinline__ void reduce_wide(const ReduceArgs& a, int bx, int blk, int grp) {
+  const long i = (long)bx * 256 + threadIdx.x;
   if (i >= a.blk_elems || !a.dest[blk]) return;
   const float* p = a.partial + ((long)grp * a.nsplit * a.nblk + blk) * a.blk_elems + i;
   const long step = (long)a.nblk * a.blk_elems;
@@ -602,12 +602,11 @@ __global__ void __launch_bounds__(256) k_reduce_partials(ReduceArgs a) {
 }
 
 // Few elements, many partials (bias-type sums): 4 threads per element take a contiguous quarter of the
-// partials each (in order), then the quarters are added in order.
-__global__ void __launch_bounds__(256) k_reduce_partials_tall(ReduceArgs a) {
-  __shared__ float sh[256];
-  const int blk = blockIdx.y, grp = blockIdx.z;
+// partials each (in order), then the quarters are added in order. sh: 256 floats of LDS. Every thread of the
+// workgroup calls it.
+__device__ __forceinline__ void reduce_tall(const ReduceArgs& a, int bx, int blk, int grp, float* sh) {
   const int e = threadIdx.x & 63, ph = threadIdx.x >> 6;
-  const long i = (long)blockIdx.x * 64 + e;
+  const long i = (long)bx * 64 + e;
   const int per = (a.nsplit + 3) / 4;
   const int k0 = ph * per;
   const int k1 = k0 + per < a.nsplit ? k0 + per : a.nsplit;
@@ -630,6 +629,66 @@ __global__ void __launch_bounds__(256) k_reduce_partials_tall(ReduceArgs a) {
   __syncthreads();
   if (ph == 0 && i < a.blk_elems) a.dest[blk][grp * a.grp_dest_stride + i] = ((sh[e] + sh[64 + e]) + sh[128 + e]) + sh[192 + e];
 }
+static bool reduce_is_tall(long blk_elems, int nsplit) { return blk_elems <= 1024 && nsplit >= 64; }
+static unsigned reduce_xblocks(long blk_elems, int nsplit) {
+  return reduce_is_tall(blk_elems, nsplit) ? (unsigned)((blk_elems + 63) / 64) : (unsigned)((blk_elems + 255) / 256);
+}
+
+__global__ void __launch_bounds__(256) k_reduce_partials(ReduceArgs a) { reduce_wide(a, blockIdx.x, blockIdx.y, blockIdx.z); }
+__global__ void __launch_bounds__(256) k_reduce_partials_tall(ReduceArgs a) {
+  __shared__ float sh[256];
+  reduce_tall(a, blockIdx.x, blockIdx.y, blockIdx.z, sh);
+}
+
+// several ungrouped reductions in one launch: blockIdx.y counts the blocks of all jobs one after the other
+constexpr int REDUCE_QUEUE_MAX = 6;
+struct ReduceQueueArgs {
+  ReduceArgs job[REDUCE_QUEUE_MAX];
+  int njobs;
+  int yoff[REDUCE_QUEUE_MAX + 1];
+  unsigned xblocks[REDUCE_QUEUE_MAX];
+  unsigned char tall[REDUCE_QUEUE_MAX];
+};
+__global__ void __launch_bounds__(256) k_reduce_queue(ReduceQueueArgs q) {
+  __shared__ float sh[256];
+  int j = 0;   // uniform over the workgroup
+  while (j + 1 < q.njobs && (int)blockIdx.y >= q.yoff[j + 1]) ++j;
+  if (blockIdx.x >= q.xblocks[j]) return;
+  const int blk = blockIdx.y - q.yoff[j];
+  if (q.tall[j]) reduce_tall(q.job[j], blockIdx.x, blk, 0, sh);
+  else reduce_wide(q.job[j], blockIdx.x, blk, 0);
+}
+
+struct ReduceQueue {
+  hipStream_t st;
+  ReduceQueueArgs q;
+};
+static thread_local ReduceQueue* tl_reduce_queue = nullptr;
+
+ReduceQueueScope::ReduceQueueScope(hipStream_t st, bool enable) : active_(enable && tl_reduce_queue == nullptr) {
+  if (active_) {
+    tl_reduce_queue = new ReduceQueue;
+    tl_reduce_queue->st = st;
+    tl_reduce_queue->q.njobs = 0;
+    tl_reduce_queue->q.yoff[0] = 0;
+  }
+}
+ReduceQueueScope::~ReduceQueueScope() {
+  if (active_) {
+    delete tl_reduce_queue;
+    tl_reduce_queue = nullptr;
+  }
+}
+int32_t ReduceQueueScope::flush() {
+  if (!active_ || tl_reduce_queue->q.njobs == 0) return HGNN_OK;
+  ReduceQueueArgs& q = tl_reduce_queue->q;
+  unsigned gx = 1;
+  for (int j = 0; j < q.njobs; ++j) gx = q.xblocks[j] > gx ? q.xblocks[j] : gx;
+  k_reduce_queue<<<dim3(gx, (unsigned)q.yoff[q.njobs], 1), 256, 0, tl_reduce_queue->st>>>(q);
+  q.njobs = 0;
+  HGNN_LAUNCH_CHECK("k_reduce_queue");
+  return HGNN_OK;
+}
 
 static int32_t launch_reduce_partials_n(hipStream_t st, const float* partial, int nsplit, int nblk, long blk_elems,
                                          float* const* dest, int ndest, int groups, long grp_dest_stride);
@@ -646,10 +705,20 @@ static int32_t launch_reduce_partials_n(hipStream_t st, const float* partial, in
   r.blk_elems = blk_elems;
   for (int i = 0; i < 8; ++i) r.dest[i] = i < ndest ? dest[i] : nullptr;
   r.grp_dest_stride = grp_dest_stride;
-  if (blk_elems <= 1024 && nsplit >= 64)
-    k_reduce_partials_tall<<<dim3((unsigned)((blk_elems + 63) / 64), nblk, groups), 256, 0, st>>>(r);
+  if (tl_reduce_queue && groups == 1 && tl_reduce_queue->q.njobs < REDUCE_QUEUE_MAX) {
+    // collected: runs with the others when the scope is flushed
+    ReduceQueueArgs& q = tl_reduce_queue->q;
+    const int j = q.njobs++;
+    q.job[j] = r;
+    q.tall[j] = reduce_is_tall(blk_elems, nsplit) ? 1 : 0;
+    q.xblocks[j] = reduce_xblocks(blk_elems, nsplit);
+    q.yoff[j + 1] = q.yoff[j] + nblk;
+    return HGNN_OK;
+  }
+  if (reduce_is_tall(blk_elems, nsplit))
+    k_reduce_partials_tall<<<dim3(reduce_xblocks(blk_elems, nsplit), nblk, groups), 256, 0, st>>>(r);
   else
-    k_reduce_partials<<<dim3((unsigned)((blk_elems + 255) / 256), nblk, groups), 256, 0, st>>>(r);
+    k_reduce_partials<<<dim3(reduce_xblocks(blk_elems, nsplit), nblk, groups), 256, 0, st>>>(r);
   HGNN_LAUNCH_CHECK("k_reduce_partials");
   return HGNN_OK;
 }

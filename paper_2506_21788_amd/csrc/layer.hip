@@ -74,7 +74,8 @@ struct LayerWs {
   unsigned* gM_pk; // [N,H/2] words: g_M as bf16 pairs (only when the fused kernels gather pairs)
   float* g_PQ;     // [N,2H]
   float* partial;  // split-K / column-sum partials of the main stream
-  float* partial2; // the same for the work that runs on the side stream
+  float* partial2; // partials of the W2 gradient
+  float* partial3; // partials of the atom-level weight gradients
   float* cs_partial;  // column-sum partials of the node weight-gradient kernel (side stream)
   float* attrpart;    // partials of the attribute rows of g_W1 (k > 1 only)
   size_t bytes;
@@ -92,11 +93,12 @@ static LayerWs carve_ws(void* p, int N, int64_t E, int H, bool bf16, int k = 1) 
   w.g_hM = c.take<float>((size_t)N * 2 * H);
   w.gM_pk = c.take<unsigned>((size_t)N * (H / 2));
   w.g_PQ = c.take<float>((size_t)N * 2 * H);
-  size_t pf = wgrad_partial_floats(H, N, 5, 1);   // the layer's five atom-level weight-gradient blocks in one launch
-  const size_t cands[3] = {colsum_partial_floats(H, N, 1), wgrad_frag_partial_floats(H), edge_bwd_colpart_floats(H)};
-  for (size_t x : cands) pf = x > pf ? x : pf;
-  w.partial = c.take<float>(pf);
-  w.partial2 = c.take<float>(pf);
+  // three regions of their own: the reductions of a reverse pass run as one launch at its end, so the partials of
+  // the edge kernel, of the W2 gradient and of the atom-level weight gradients all live until then
+  const size_t pc = colsum_partial_floats(H, N, 1), pe = edge_bwd_colpart_floats(H);
+  w.partial = c.take<float>(pc > pe ? pc : pe);
+  w.partial2 = c.take<float>(wgrad_frag_partial_floats(H));
+  w.partial3 = c.take<float>(wgrad_partial_floats(H, N, 5, 1));   // the layer's five atom-level blocks in one launch
   w.cs_partial = c.take<float>(wgrad_colsum_partial_floats(H, N));
   w.attrpart = k > 1 ? c.take<float>(edge_bwd_attrpart_floats(H)) : nullptr;
   w.bytes = c.used();
@@ -384,6 +386,9 @@ static int32_t mp_layer_bwd_impl(void* stream, int32_t N, int64_t E, int32_t H, 
   HGNN_REQUIRE(ss.ok, HGNN_ERR_HIP, "could not create the side stream");
   hipStream_t sx = side_stream_enabled(false) ? ss.s : st;
   HGNN_TRY(stream_after(sx, st, ss.ev[0]));   // inputs of this call are ready on the side stream too
+  // one stream: the four reductions of split partials below (edge kernel sums, W2 gradient, atom-level weight
+  // gradients and their bias sums) run as one launch at the end; nothing in this call reads their results
+  ReduceQueueScope reductions(st, sx == st);
 
   // every gradient field is written below even when there is nothing to sum over
   {  // g_z3 = (g_h' W4^T) * silu'(z3), and from the same tile [g_h' + g_h(a) | g_M] = g_z3 W3^T (+ g_h' on the first half)
@@ -476,8 +481,12 @@ static int32_t mp_layer_bwd_impl(void* stream, int32_t N, int64_t E, int32_t H, 
     j[2].dest[0] = gW + o.W1; j[2].dest[1] = gW + o.W1 + HH;
     j[2].colsum_dest[0] = gW + o.b1;
     for (auto& a : j) a.M = N;
-    j[0].partial = w.partial2; j[0].colsum_partial = w.cs_partial;
+    j[0].partial = w.partial3; j[0].colsum_partial = w.cs_partial;
     HGNN_TRY(launch_wgrad_multi(sx, H, bf16, j, 3));
+  }
+  {
+    ProfScope ps(PT_MISC, st);
+    HGNN_TRY(reductions.flush());
   }
   HGNN_TRY(stream_after(st, sx, ss.ev[4]));   // join: the caller's stream now also orders after every gradient
   if (g_v_in != g_v_out) HGNN_TRY(launch_copy_f32(st, g_v_out, g_v_in, (int64_t)N * 3));
