@@ -587,6 +587,10 @@ __device__ __forceinline__ void reduce_wide(const ReduceArgs& a, int bx, int blk
   if (i >= a.blk_elems || !a.dest[blk]) return;
   const float* p = a.partial + ((long)grp * a.nsplit * a.nblk + blk) * a.blk_elems + i;
   const long step = (long)a.nblk * a.blk_elems;
+  if (a.nsplit == 1) {   // a plain copy (also of negative zeros)
+    a.dest[blk][grp * a.grp_dest_stride + i] = p[0];
+    return;
+  }
   // ascending order of the partials is kept; sixteen loads are in flight at a time
   float s = 0.f;
   int k = 0;

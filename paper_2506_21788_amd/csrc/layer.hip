@@ -486,10 +486,13 @@ static int32_t mp_layer_bwd_impl(void* stream, int32_t N, int64_t E, int32_t H, 
   }
   {
     ProfScope ps(PT_MISC, st);
+    if (g_v_in != g_v_out && N > 0) {   // g_v passes through: a reduction of one partial is a copy (joins the launch below)
+      float* dest[4] = {g_v_in, nullptr, nullptr, nullptr};
+      HGNN_TRY(launch_reduce_partials(st, g_v_out, 1, 1, (long)N * 3, dest, 1, 0));
+    }
     HGNN_TRY(reductions.flush());
   }
   HGNN_TRY(stream_after(st, sx, ss.ev[4]));   // join: the caller's stream now also orders after every gradient
-  if (g_v_in != g_v_out) HGNN_TRY(launch_copy_f32(st, g_v_out, g_v_in, (int64_t)N * 3));
   return HGNN_OK;
 }
 
