@@ -131,7 +131,7 @@ int32_t launch_colsum(hipStream_t st, int H, const ColsumArgs& a);
 int32_t launch_reduce_partials(hipStream_t st, const float* partial, int nsplit, int nblk, long blk_elems,
                                float* const dest[4], int groups, long grp_dest_stride);
 
-// While a ReduceQueueScope is alive on this host thread, reductions of ungrouped partials (the ones above, also the
+// While a ReduceQueueScope is alive on this host thread, reductions of split partials (the ones above, also the
 // ones the weight-gradient and edge kernels' launchers ask for) are collected instead of launched; flush() runs
 // them all as one launch on the scope's stream. The caller keeps every partial buffer untouched until then, and
 // nothing it enqueues before the flush may read a reduction's result. A scope that is destroyed without a flush

@@ -644,23 +644,25 @@ __global__ void __launch_bounds__(256) k_reduce_partials_tall(ReduceArgs a) {
   reduce_tall(a, blockIdx.x, blockIdx.y, blockIdx.z, sh);
 }
 
-// several ungrouped reductions in one launch: blockIdx.y counts the blocks of all jobs one after the other
+// several reductions in one launch: blockIdx.y counts the blocks of all jobs one after the other, blockIdx.z the
+// groups of the job with the most groups
 constexpr int REDUCE_QUEUE_MAX = 6;
 struct ReduceQueueArgs {
   ReduceArgs job[REDUCE_QUEUE_MAX];
   int njobs;
   int yoff[REDUCE_QUEUE_MAX + 1];
   unsigned xblocks[REDUCE_QUEUE_MAX];
+  int groups[REDUCE_QUEUE_MAX];
   unsigned char tall[REDUCE_QUEUE_MAX];
 };
 __global__ void __launch_bounds__(256) k_reduce_queue(ReduceQueueArgs q) {
   __shared__ float sh[256];
   int j = 0;   // uniform over the workgroup
   while (j + 1 < q.njobs && (int)blockIdx.y >= q.yoff[j + 1]) ++j;
-  if (blockIdx.x >= q.xblocks[j]) return;
+  if (blockIdx.x >= q.xblocks[j] || (int)blockIdx.z >= q.groups[j]) return;
   const int blk = blockIdx.y - q.yoff[j];
-  if (q.tall[j]) reduce_tall(q.job[j], blockIdx.x, blk, 0, sh);
-  else reduce_wide(q.job[j], blockIdx.x, blk, 0);
+  if (q.tall[j]) reduce_tall(q.job[j], blockIdx.x, blk, blockIdx.z, sh);
+  else reduce_wide(q.job[j], blockIdx.x, blk, blockIdx.z);
 }
 
 struct ReduceQueue {
@@ -686,9 +688,12 @@ ReduceQueueScope::~ReduceQueueScope() {
 int32_t ReduceQueueScope::flush() {
   if (!active_ || tl_reduce_queue->q.njobs == 0) return HGNN_OK;
   ReduceQueueArgs& q = tl_reduce_queue->q;
-  unsigned gx = 1;
-  for (int j = 0; j < q.njobs; ++j) gx = q.xblocks[j] > gx ? q.xblocks[j] : gx;
-  k_reduce_queue<<<dim3(gx, (unsigned)q.yoff[q.njobs], 1), 256, 0, tl_reduce_queue->st>>>(q);
+  unsigned gx = 1, gz = 1;
+  for (int j = 0; j < q.njobs; ++j) {
+    gx = q.xblocks[j] > gx ? q.xblocks[j] : gx;
+    gz = (unsigned)q.groups[j] > gz ? (unsigned)q.groups[j] : gz;
+  }
+  k_reduce_queue<<<dim3(gx, (unsigned)q.yoff[q.njobs], gz), 256, 0, tl_reduce_queue->st>>>(q);
   q.njobs = 0;
   HGNN_LAUNCH_CHECK("k_reduce_queue");
   return HGNN_OK;
@@ -709,13 +714,14 @@ static int32_t launch_reduce_partials_n(hipStream_t st, const float* partial, in
   r.blk_elems = blk_elems;
   for (int i = 0; i < 8; ++i) r.dest[i] = i < ndest ? dest[i] : nullptr;
   r.grp_dest_stride = grp_dest_stride;
-  if (tl_reduce_queue && groups == 1 && tl_reduce_queue->q.njobs < REDUCE_QUEUE_MAX) {
+  if (tl_reduce_queue && groups >= 1 && groups <= 65535 && tl_reduce_queue->q.njobs < REDUCE_QUEUE_MAX) {
     // collected: runs with the others when the scope is flushed
     ReduceQueueArgs& q = tl_reduce_queue->q;
     const int j = q.njobs++;
     q.job[j] = r;
     q.tall[j] = reduce_is_tall(blk_elems, nsplit) ? 1 : 0;
     q.xblocks[j] = reduce_xblocks(blk_elems, nsplit);
+    q.groups[j] = groups;
     q.yoff[j + 1] = q.yoff[j] + nblk;
     return HGNN_OK;
   }

@@ -524,6 +524,9 @@ static HeadSaved carve_head_saved(void* p, int N, int G, int Hh) {
 struct HeadWs {
   void* packed;  // [S][2] blocks
   float *g_ze, *g_zf, *gq, *partial;
+  // reverse pass: partials of the two column sums and of the weight gradient of each branch (energy, force); they all
+  // live until the pass's one reduction launch
+  float *pcs[2][2], *pwg[2];
   size_t bytes;
 };
 static HeadWs carve_head_ws(void* p, int N, int G, int H, int Hh, int S, bool bf16) {
@@ -537,6 +540,12 @@ static HeadWs carve_head_ws(void* p, int N, int G, int H, int Hh, int S, bool bf
   size_t pf = wgrad_partial_floats(H, mx, 1, S);
   size_t cf = colsum_partial_floats(H, mx, S);
   w.partial = c.take<float>(pf > cf ? pf : cf);
+  for (int br = 0; br < 2; ++br) {
+    const int64_t M = br == 0 ? G : N;
+    w.pcs[br][0] = c.take<float>(colsum_partial_floats(H, M, S));
+    w.pcs[br][1] = c.take<float>(colsum_partial_floats(H, M, S));
+    w.pwg[br] = c.take<float>(wgrad_partial_floats(H, M, 1, S));
+  }
   w.bytes = c.used();
   return w;
 }
@@ -807,7 +816,9 @@ extern "C" int32_t hgnn_multihead_decode_bwd(void* stream, int32_t N, int32_t G,
   }
   HGNN_LAUNCH_CHECK("k_head_out_bwd");
 
-  // ---- energy branch (rows = graphs) and force branch (rows = atoms), same five steps each
+  // ---- energy branch (rows = graphs) and force branch (rows = atoms), same five steps each; their six reductions
+  // of split partials (nothing here reads a result) run as one launch at the end
+  ReduceQueueScope reductions(st, true);
   for (int br = 0; br < 2; ++br) {
     const bool en = br == 0;
     const int64_t M = en ? G : N;
@@ -827,7 +838,7 @@ extern "C" int32_t hgnn_multihead_decode_bwd(void* stream, int32_t N, int32_t G,
     {  // second layer weight and bias
       ColsumArgs c;
       c.X = z; c.ldx = Hh; c.f_silu = 1; c.w = gout; c.row_idx = ridx; c.grp_ptr = gptr; c.S = S; c.M = M;
-      c.dest = gWhead + oW2; c.grp_dest_stride = o.per; c.partial = w.partial;
+      c.dest = gWhead + oW2; c.grp_dest_stride = o.per; c.partial = w.pcs[br][0];
       HGNN_TRY(launch_colsum(st, Hh, c));
       k_group_scalar_sum<<<S, 1024, 0, st>>>(gout, ridx, gptr, gWhead + ob2, o.per);
       HGNN_LAUNCH_CHECK("k_group_scalar_sum");
@@ -835,14 +846,14 @@ extern "C" int32_t hgnn_multihead_decode_bwd(void* stream, int32_t N, int32_t G,
     {  // first layer bias and weight
       ColsumArgs c;
       c.X = gz; c.ldx = Hh; c.row_idx = ridx; c.grp_ptr = gptr; c.S = S; c.M = M;
-      c.dest = gWhead + ob1; c.grp_dest_stride = o.per; c.partial = w.partial;
+      c.dest = gWhead + ob1; c.grp_dest_stride = o.per; c.partial = w.pcs[br][1];
       HGNN_TRY(launch_colsum(st, Hh, c));
       WgradArgs a;
       a.A[0] = X; a.lda[0] = H;
       a.B[0] = gz; a.ldb[0] = Hh;
       a.row_idx = ridx; a.grp_ptr = gptr; a.S = S; a.M = M;
       a.dest[0] = gWhead + oW1; a.grp_dest_stride = o.per;
-      a.partial = w.partial;
+      a.partial = w.pwg[br];
       HGNN_TRY(launch_wgrad(st, H, bf16, a));
     }
     {  // input gradient
@@ -853,6 +864,10 @@ extern "C" int32_t hgnn_multihead_decode_bwd(void* stream, int32_t N, int32_t G,
       g.C = en ? g_p : g_h; g.ldc = H;
       HGNN_TRY(launch_gemm(st, H, bf16, g));
     }
+  }
+  {
+    ProfScope ps(PT_COLSUM, st);
+    HGNN_TRY(reductions.flush());
   }
   return HGNN_OK;
 }
