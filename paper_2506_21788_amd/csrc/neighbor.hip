@@ -194,6 +194,12 @@ constexpr float FRAC_TOL = 1e-5f;
 constexpr float BIN_MARGIN = 1.001f;  // bins are at least 1.001 * rc wide: absorbs float32 binning error
 constexpr int NB_MAX = 256;
 
+// two ranges in one launch (n2 <= n1)
+__global__ void k_fill2_i32(int32_t* p1, int64_t n1, int32_t* p2, int64_t n2, int32_t v) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n1) p1[i] = v;
+  if (i < n2) p2[i] = v;
+}
 __global__ void k_fill_i32(int32_t* p, int64_t n, int32_t v) {
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = v;
@@ -728,11 +734,13 @@ __global__ void __launch_bounds__(256) k_search(SearchArgs p) {
 // stores the hits unordered and ranks them from memory
 // ---------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(256)
-k_long_rows_hits(const int32_t* __restrict__ novf, const int32_t* __restrict__ ovf_rows, const float* __restrict__ pos,
-                 const GMeta* __restrict__ meta, const int32_t* __restrict__ atom_graph,
-                 const int32_t* __restrict__ atom_bin, const int32_t* __restrict__ bin_start,
-                 const int32_t* __restrict__ bin_atoms, float rc, const int32_t* __restrict__ row_ptr,
-                 int32_t* __restrict__ key_j, int32_t* __restrict__ key_c) {
+k_long_rows(const int32_t* __restrict__ novf, const int32_t* __restrict__ ovf_rows, const float* __restrict__ pos,
+            const GMeta* __restrict__ meta, const int32_t* __restrict__ atom_graph,
+            const int32_t* __restrict__ atom_bin, const int32_t* __restrict__ bin_start,
+            const int32_t* __restrict__ bin_atoms, float rc, const int32_t* __restrict__ row_ptr,
+            int32_t* key_j, int32_t* key_c, int32_t* __restrict__ dst, int32_t* __restrict__ col,
+            int8_t* __restrict__ shift, float* __restrict__ d2, float* __restrict__ rvec,
+            const int32_t* __restrict__ colT_ptr, int32_t* __restrict__ colT_cur, int32_t* __restrict__ unsorted) {
   const int w0 = (int)(((size_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6);
   const int nw = (int)(((size_t)gridDim.x * blockDim.x) >> 6);
   const int lane = threadIdx.x & 63;
@@ -787,25 +795,10 @@ k_long_rows_hits(const int32_t* __restrict__ novf, const int32_t* __restrict__ o
         }
       }
     }
-  }
-}
-
-__global__ void __launch_bounds__(256)
-k_long_rows_emit(const int32_t* __restrict__ novf, const int32_t* __restrict__ ovf_rows, const float* __restrict__ pos,
-                 const GMeta* __restrict__ meta, const int32_t* __restrict__ atom_graph,
-                 const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ key_j,
-                 const int32_t* __restrict__ key_c, int32_t* __restrict__ dst, int32_t* __restrict__ col,
-                 int8_t* __restrict__ shift, float* __restrict__ d2, float* __restrict__ rvec,
-                 const int32_t* __restrict__ colT_ptr, int32_t* __restrict__ colT_cur, int32_t* __restrict__ unsorted) {
-  const int w0 = (int)(((size_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6);
-  const int nw = (int)(((size_t)gridDim.x * blockDim.x) >> 6);
-  const int lane = threadIdx.x & 63;
-  const int n = *novf;
-  for (int r = w0; r < n; r += nw) {
-    const int i = ovf_rows[r];
+    // the row's hits are in memory: every lane of this wavefront reads them all below
+    __threadfence();
+    __builtin_amdgcn_wave_barrier();
     const int start = row_ptr[i], end = row_ptr[i + 1];
-    const GMeta& m = meta[atom_graph[i]];
-    const float pix = pos[3 * (size_t)i], piy = pos[3 * (size_t)i + 1], piz = pos[3 * (size_t)i + 2];
     for (int t = start + lane; t < end; t += 64) {
       const int mj = key_j[t], mc = key_c[t];
       int rank = 0;
@@ -1073,9 +1066,8 @@ extern "C" int32_t hgnn_radius_graph_fill(void* stream, int32_t N, int32_t G, co
   int32_t* key_j = static_cast<int32_t*>(tmp);
   int32_t* key_c = key_j + E;
   // this call's own counters start at zero, so that a second fill after one count works as the first
-  k_fill_i32<<<nblk((int64_t)N + 1, 256), 256, 0, st>>>(w.colT_cur, (int64_t)N + 1, 0);
-  k_fill_i32<<<1, 64, 0, st>>>(w.status + 2, 1, 0);
-  HGNN_LAUNCH_CHECK("k_fill_i32");
+  k_fill2_i32<<<nblk((int64_t)N + 1, 256), 256, 0, st>>>(w.colT_cur, (int64_t)N + 1, w.status + 2, 1, 0);
+  HGNN_LAUNCH_CHECK("k_fill2_i32");
   if (E > 0) {
     {
       ProfScope ps(PT_NEIGH_FILL, st);
@@ -1088,12 +1080,10 @@ extern "C" int32_t hgnn_radius_graph_fill(void* stream, int32_t N, int32_t G, co
     ProfScope ps(PT_NEIGH_EMIT, st);
     // rows longer than the LDS row (their number is only known on the device: a fixed grid walks the list)
     const unsigned lgrid = N < 256 ? nblk((int64_t)N * 64, 256) : 64;
-    k_long_rows_hits<<<lgrid, 256, 0, st>>>(w.status + 2, w.ovf_rows, pos, w.meta, w.atom_graph, w.atom_bin, w.bin_start,
-                                            w.bin_atoms, rc, row_ptr, key_j, key_c);
-    HGNN_LAUNCH_CHECK("k_long_rows_hits");
-    k_long_rows_emit<<<lgrid, 256, 0, st>>>(w.status + 2, w.ovf_rows, pos, w.meta, w.atom_graph, row_ptr, key_j, key_c,
-                                            dst, col, shift, d2, rvec, w.colT_ptr, w.colT_cur, permT);
-    HGNN_LAUNCH_CHECK("k_long_rows_emit");
+    k_long_rows<<<lgrid, 256, 0, st>>>(w.status + 2, w.ovf_rows, pos, w.meta, w.atom_graph, w.atom_bin, w.bin_start,
+                                       w.bin_atoms, rc, row_ptr, key_j, key_c, dst, col, shift, d2, rvec, w.colT_ptr,
+                                       w.colT_cur, permT);
+    HGNN_LAUNCH_CHECK("k_long_rows");
   }
   ProfScope pst(PT_NEIGH_TRANSPOSE, st);
   k_edge_graph_ptr<<<nblk(G + 1, 256), 256, 0, st>>>(G, graph_off, row_ptr, edge_graph_ptr);
