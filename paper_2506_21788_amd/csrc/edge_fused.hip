@@ -1159,7 +1159,7 @@ int32_t launch_edge_cvec(hipStream_t st, int64_t E, const int32_t* dst, const fl
 // ATTR: k > 1 edge attributes take the place of d2 (at / att: this tile's attributes in LDS, edge-major and
 // slot-major; *_next / nxa: where and what to store for the next tile; bW1a: the attribute weights as matrix-core
 // operands; gacc: running g_W1a of this wavefront's columns, slots in the accumulator rows).
-template <int H, bool BF16, bool FULL, bool ATTR>
+template <int H, bool BF16, bool FULL, bool ATTR, bool DSUM>
 __device__ __forceinline__ void edge_bwd_tile(const EdgeBwdArgs& p, unsigned char* smem, const int* s, int* s_next,
                                               int nxt, int tile, int E, int tid, int wr, int wc, int lane,
                                               const float (&w1d)[ECfg<H, BF16>::CB], const float (&wxn)[ECfg<H, BF16>::CB],
@@ -1174,6 +1174,17 @@ __device__ __forceinline__ void edge_bwd_tile(const EdgeBwdArgs& p, unsigned cha
   const int g = lane >> 5, x = lane & 31;
   // byte offset of this lane's first column inside a row: word wc*32 + x of bf16 pairs, else column wc*CB*32 + x
   const unsigned colb = (unsigned)((PAIRS ? wc * 32 : wc * C::CB * 32) + x) * 4u;
+  static_assert(!DSUM || (PAIRS && !ATTR), "the in-kernel destination sums take bf16 pairs without attributes");
+  // DSUM: the last phase also leaves the tile's g_z1 words row-major in LDS (row pitch of the A tile, which is no
+  // longer needed then); this lane writes word wc*32 + x of the rows 4g + (constant)
+  constexpr int DPITCH = C::STRIDE / 2;
+  unsigned* dsw = reinterpret_cast<unsigned*>(smem) + (4 * g) * DPITCH + wc * 32 + x;
+  // the destinations of the edges next to the tile decide whether its first and last row are complete here
+  int dprev = -1, dnext = -1;
+  if constexpr (DSUM) {
+    if (tile > 0) dprev = p.dst[(size_t)tile * C::TM - 1];
+    if ((tile + 1) * C::TM < E) dnext = p.dst[(size_t)(tile + 1) * C::TM];
+  }
   // ---- g_z2 = (alpha*g_M[dst] + c*wx) * silu'(z2): operand-packed to memory, row-major to LDS
   if constexpr (PAIRS && FULL) {
     // groups of 8 edges, software-pipelined: the loads of the next group are in flight while this one is processed
@@ -1343,7 +1354,9 @@ __device__ __forceinline__ void edge_bwd_tile(const EdgeBwdArgs& p, unsigned cha
           sw1[0] += dd[u] * g0;
           sw1[1] += dd[u] * g1;
         }
-        stg_nt<unsigned>(o, lane * 4u + u * 256u, pack_bf16x2(g0, g1));
+        const unsigned pw = pack_bf16x2(g0, g1);
+        stg_nt<unsigned>(o, lane * 4u + u * 256u, pw);
+        if constexpr (DSUM) dsw[(rblk * 32 + 8 * (2 * vh + (u >> 2)) + (u & 3)) * DPITCH] = pw;
       }
       if constexpr (ATTR) {
         const bf16x8_t aT = attr_t_operand(att, rblk, vh, lane);
@@ -1391,7 +1404,11 @@ __device__ __forceinline__ void edge_bwd_tile(const EdgeBwdArgs& p, unsigned cha
       if constexpr (PAIRS) {
         char* o = uoff(p.gz1_vm, (((size_t)eb * (C::NCB / 2) + wc) * 16 + 8 * vh) * 256);
 #pragma unroll
-        for (int u = 0; u < 8; ++u) stg_nt<unsigned>(o, lane * 4u + u * 256u, pack_bf16x2(gv[0][u], gv[1][u]));
+        for (int u = 0; u < 8; ++u) {
+          const unsigned pw = pack_bf16x2(gv[0][u], gv[1][u]);
+          stg_nt<unsigned>(o, lane * 4u + u * 256u, pw);
+          if constexpr (DSUM) dsw[(rblk * 32 + 8 * (2 * vh + (u >> 2)) + (u & 3)) * DPITCH] = pw;
+        }
       } else {
 #pragma unroll
         for (int j = 0; j < C::CB; ++j) {
@@ -1415,9 +1432,83 @@ __device__ __forceinline__ void edge_bwd_tile(const EdgeBwdArgs& p, unsigned cha
       for (int j = 0; j < C::CB; ++j) asm volatile("" : "+v"(sw1[j]));
     }
   }
+  // ---- g_P: the tile's g_z1 words summed per destination out of LDS. The edges are sorted by destination, so a row
+  // is a run of consecutive edges. A thread owns one word (two columns) of one 32-edge half of the tile and adds the
+  // half's edges in order; where the destination changes (the same place for every thread of a wavefront: scalar
+  // branches on one ballot mask) the finished run goes to g_P when it is the whole row, otherwise to the half's partial
+  // slot: slot 1 when the row starts in this half, slot 0 when it started earlier. k_dsum_fix adds a row's slots.
+  if constexpr (DSUM) {
+    __syncthreads();
+    const unsigned* gw = reinterpret_cast<const unsigned*>(smem);
+    const int hf = __builtin_amdgcn_readfirstlane(tid >> 7);
+    const int w = tid & 127;
+    const int dl = s[lane];
+    const int dq = s[lane ? lane - 1 : 0];
+    const unsigned long long starts = __ballot(dl != (lane ? dq : dprev));   // bit r: edge r of the tile starts a row
+    const int ge0 = tile * C::TM + 32 * hf;
+    const int nvalid = FULL ? 32 : (E - ge0 < 32 ? E - ge0 : 32);
+    if (FULL || nvalid > 0) {
+      unsigned wd[32];
+#pragma unroll
+      for (int k = 0; k < 32; ++k) wd[k] = (FULL || k < nvalid) ? gw[(32 * hf + k) * DPITCH + w] : 0u;
+      const unsigned m32 = (unsigned)(starts >> (32 * hf));
+      const bool ends = ge0 + 32 >= E ||
+                        (hf == 0 ? ((starts >> 32) & 1ull) != 0ull : dnext != __builtin_amdgcn_readfirstlane(s[63]));
+      float a0 = 0.f, a1 = 0.f;
+      int k0 = 0;
+      bool sf = (m32 & 1u) != 0u;   // the run at hand starts its row
+      auto flush = [&](bool ef) {
+        const int d = __builtin_amdgcn_readfirstlane(s[32 * hf + k0]);
+        float* o = (sf && ef) ? p.gP + (size_t)d * p.ldgP : p.dpart + ((size_t)(ge0 >> 5) * 2 + (sf ? 1 : 0)) * H;
+        o[(w >> 5) * 64 + (w & 31)] = a0;
+        o[(w >> 5) * 64 + 32 + (w & 31)] = a1;
+      };
+#pragma unroll
+      for (int k = 0; k < 32; ++k) {
+        if (k > 0 && ((m32 >> k) & 1u) && (FULL || k < nvalid)) {
+          flush(true);
+          a0 = a1 = 0.f;
+          k0 = k;
+          sf = true;
+        }
+        if (FULL || k < nvalid) {
+          a0 += __uint_as_float(wd[k] << 16);
+          a1 += __uint_as_float(wd[k] & 0xffff0000u);
+        }
+      }
+      flush(ends);
+    }
+    __syncthreads();   // the next tile's first phase writes the A tile again
+  }
 }
 
-template <int H, bool BF16, bool ATTR>
+// g_P rows that k_edge_bwd could not finish inside one 32-edge unit: the partial of the unit in which the row starts
+// (slot 1) plus the partials of the later units (slot 0), in unit order; empty rows are set to zero. One wavefront per
+// atom, four columns per lane.
+template <int H>
+__global__ void __launch_bounds__(256) k_dsum_fix(int N, const int32_t* __restrict__ row_ptr,
+                                                   const float* __restrict__ dpart, float* __restrict__ gP, int ldgP) {
+  static_assert(H == 256, "four columns per lane");
+  const int i = (int)(((size_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6);
+  const int lane = threadIdx.x & 63;
+  if (i >= N) return;
+  const int ra = row_ptr[i], rb = row_ptr[i + 1];
+  float4* o = reinterpret_cast<float4*>(gP + (size_t)i * ldgP) + lane;
+  if (ra == rb) {
+    *o = make_float4(0.f, 0.f, 0.f, 0.f);
+    return;
+  }
+  const int u0 = ra >> 5, uk = (rb - 1) >> 5;
+  if (u0 == uk) return;
+  float4 a = reinterpret_cast<const float4*>(dpart + ((size_t)u0 * 2 + 1) * H)[lane];
+  for (int u = u0 + 1; u <= uk; ++u) {
+    const float4 b = reinterpret_cast<const float4*>(dpart + (size_t)u * 2 * H)[lane];
+    a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
+  }
+  *o = a;
+}
+
+template <int H, bool BF16, bool ATTR, bool DSUM>
 __global__ void __launch_bounds__(256, ATTR ? 2 : 3) k_edge_bwd(EdgeBwdArgs p, int ntiles) {
   using C = ECfg<H, BF16>;
   static_assert(!ATTR || (BF16 && C::TM == 64), "edge attributes: bf16 operands, 64-edge tiles");
@@ -1468,10 +1559,10 @@ __global__ void __launch_bounds__(256, ATTR ? 2 : 3) k_edge_bwd(EdgeBwdArgs p, i
     unsigned short* at_next = atb + (buf ^ 1) * ATTR_TILE;
     unsigned short* att_next = attb + (buf ^ 1) * ATTR_T_TILE;
     if ((tile + 1) * C::TM <= E)
-      edge_bwd_tile<H, BF16, true, ATTR>(p, smem, s, s_next, nxt, tile, E, tid, wr, wc, lane, w1d, wxn, sb2, swx, sw1, at, att,
+      edge_bwd_tile<H, BF16, true, ATTR, DSUM>(p, smem, s, s_next, nxt, tile, E, tid, wr, wc, lane, w1d, wxn, sb2, swx, sw1, at, att,
                                          at_next, att_next, nxa, bW1a, gacc);
     else
-      edge_bwd_tile<H, BF16, false, ATTR>(p, smem, s, s_next, nxt, tile, E, tid, wr, wc, lane, w1d, wxn, sb2, swx, sw1, at, att,
+      edge_bwd_tile<H, BF16, false, ATTR, DSUM>(p, smem, s, s_next, nxt, tile, E, tid, wr, wc, lane, w1d, wxn, sb2, swx, sw1, at, att,
                                           at_next, att_next, nxa, bW1a, gacc);
   }
   // ---- per-column partial sums of this wavefront: combine the two lane halves, one writer per column
@@ -1503,16 +1594,16 @@ constexpr int EDGE_BWD_MAX_GRID = 2048;
 size_t edge_bwd_colpart_floats(int H) { return (size_t)EDGE_BWD_MAX_GRID * 2 * 3 * H; }
 size_t edge_bwd_attrpart_floats(int H) { return (size_t)EDGE_BWD_MAX_GRID * 2 * ATTR_K * H; }
 
-template <int H, bool BF16, bool ATTR>
+template <int H, bool BF16, bool ATTR, bool DSUM = false>
 static int32_t launch_edge_bwd_t(hipStream_t st, const EdgeBwdArgs& a) {
   using C = ECfg<H, BF16>;
   const int64_t ntiles = (a.E + C::TM - 1) / C::TM;
   constexpr size_t lds = C::LDS_BYTES + 8 * C::TM * 4 + (ATTR ? 2 * (ATTR_TILE + ATTR_T_TILE) * 2 : 0);
   static int per_cu = 0;
   if (!per_cu) {
-    HGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_edge_bwd<H, BF16, ATTR>),
+    HGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_edge_bwd<H, BF16, ATTR, DSUM>),
                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    per_cu = resident_per_cu(reinterpret_cast<const void*>(&k_edge_bwd<H, BF16, ATTR>), lds, ATTR ? 2 : 3);
+    per_cu = resident_per_cu(reinterpret_cast<const void*>(&k_edge_bwd<H, BF16, ATTR, DSUM>), lds, ATTR ? 2 : 3);
   }
   int64_t grid = (int64_t)num_cus() * per_cu;
   if (grid > EDGE_BWD_MAX_GRID) grid = EDGE_BWD_MAX_GRID;
@@ -1520,8 +1611,13 @@ static int32_t launch_edge_bwd_t(hipStream_t st, const EdgeBwdArgs& a) {
   if (grid < 1) grid = 1;  // E == 0: one block writes zero partials
   {
     ProfScope ps(PT_EDGE_FUSED_BWD, st);
-    k_edge_bwd<H, BF16, ATTR><<<dim3((unsigned)grid), 256, lds, st>>>(a, (int)ntiles);
+    k_edge_bwd<H, BF16, ATTR, DSUM><<<dim3((unsigned)grid), 256, lds, st>>>(a, (int)ntiles);
     HGNN_LAUNCH_CHECK("k_edge_bwd");
+  }
+  if constexpr (DSUM) {
+    ProfScope ps(PT_SEGSUM_DST, st);
+    k_dsum_fix<H><<<dim3((unsigned)(((int64_t)a.N * 64 + 255) / 256)), 256, 0, st>>>(a.N, a.row_ptr, a.dpart, a.gP, a.ldgP);
+    HGNN_LAUNCH_CHECK("k_dsum_fix");
   }
   float* dest[4] = {a.g_b2, a.g_wx, a.g_w1d, nullptr};
   HGNN_TRY(launch_reduce_partials(st, a.colpart, (int)grid * C::WR, 3, H, dest, 1, 0));
@@ -1537,6 +1633,9 @@ int32_t launch_edge_bwd(hipStream_t st, int H, bool bf16, const EdgeBwdArgs& a) 
                (long long)a.E);
   HGNN_REQUIRE(a.ldgM == (edge_pairs(H, bf16) ? H / 2 : 2 * H), HGNN_ERR_BAD_SHAPE,
                "g_M must be the second half of a [N,2H] tensor, or [N,H/2] words of bf16 pairs");
+  HGNN_REQUIRE(!a.gP || (edge_pairs(H, bf16) && a.k <= 1 && a.dpart && a.row_ptr && a.N > 0 && a.ldgP >= H &&
+                         a.ldgP % 4 == 0),
+               HGNN_ERR_BAD_SHAPE, "in-kernel destination sums: bf16 operands at H = 256 without edge attributes");
   if (a.k > 1) {
     HGNN_REQUIRE(bf16 && a.k <= ATTR_K && a.W1a && a.attrpart && a.g_W1a && (a.attr || a.E == 0), HGNN_ERR_BAD_SHAPE,
                  "edge attributes on the fused kernels: bf16 operands, 2 <= k <= %d", ATTR_K);
@@ -1550,7 +1649,9 @@ int32_t launch_edge_bwd(hipStream_t st, int H, bool bf16, const EdgeBwdArgs& a) 
   switch (H) {
     case 64: return bf16 ? launch_edge_bwd_t<64, true, false>(st, a) : launch_edge_bwd_t<64, false, false>(st, a);
     case 128: return bf16 ? launch_edge_bwd_t<128, true, false>(st, a) : launch_edge_bwd_t<128, false, false>(st, a);
-    case 256: return bf16 ? launch_edge_bwd_t<256, true, false>(st, a) : launch_edge_bwd_t<256, false, false>(st, a);
+    case 256:
+      if (bf16 && a.gP) return launch_edge_bwd_t<256, true, false, true>(st, a);
+      return bf16 ? launch_edge_bwd_t<256, true, false>(st, a) : launch_edge_bwd_t<256, false, false>(st, a);
   }
   return set_error(HGNN_ERR_BAD_SHAPE, "H must be 64, 128 or 256 (got %d)", H);
 }

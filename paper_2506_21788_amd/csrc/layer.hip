@@ -78,6 +78,7 @@ struct LayerWs {
   float* partial3; // partials of the atom-level weight gradients
   float* cs_partial;  // column-sum partials of the node weight-gradient kernel (side stream)
   float* attrpart;    // partials of the attribute rows of g_W1 (k > 1 only)
+  float* dpart;       // per-unit partials of the destination sums formed inside the reverse edge kernel
   size_t bytes;
 };
 
@@ -101,6 +102,7 @@ static LayerWs carve_ws(void* p, int N, int64_t E, int H, bool bf16, int k = 1) 
   w.partial3 = c.take<float>(wgrad_partial_floats(H, N, 5, 1));   // the layer's five atom-level blocks in one launch
   w.cs_partial = c.take<float>(wgrad_colsum_partial_floats(H, N));
   w.attrpart = k > 1 ? c.take<float>(edge_bwd_attrpart_floats(H)) : nullptr;
+  w.dpart = edge_pairs(H, bf16) && k <= 1 ? c.take<float>(edge_bwd_dpart_floats(E, H)) : nullptr;
   w.bytes = c.used();
   return w;
 }
@@ -413,6 +415,11 @@ static int32_t mp_layer_bwd_impl(void* stream, int32_t N, int64_t E, int32_t H, 
   // every CU by itself, so the side stream is drained first instead of competing with it.
   HGNN_TRY(launch_edge_cvec(st, E, dst, rvec, g_v_out, alpha, w.cvec));
   HGNN_TRY(stream_after(st, sx, ss.ev[5]));
+  // With bf16 pairs the reverse edge kernel also sums g_z1 per destination (out of the tile it holds in LDS), unless
+  // the gradient with respect to d2 is asked for, which the separate pass over g_z1 forms on its way.
+  // HGNN_DSUM_IN_KERNEL=0 keeps the separate pass (for comparing the two).
+  const char* dsum_env = getenv("HGNN_DSUM_IN_KERNEL");
+  const bool dsum_in_kernel = edge_pairs(H, bf16) && k <= 1 && !g_d2 && N > 0 && !(dsum_env && dsum_env[0] == '0');
   {
     EdgeBwdArgs e;
     e.E = E; e.dst = dst; e.col = col;
@@ -432,6 +439,9 @@ static int32_t mp_layer_bwd_impl(void* stream, int32_t N, int64_t E, int32_t H, 
     e.gz2_pk = w.gz2_pk; e.gz1_vm = w.gz1_vm;
     e.colpart = w.partial;
     e.g_b2 = gW + o.b2; e.g_wx = gW + o.wx; e.g_w1d = k > 1 ? nullptr : gW + o.W1 + 2 * HH;
+    if (dsum_in_kernel) {
+      e.gP = w.g_PQ; e.ldgP = 2 * H; e.dpart = w.dpart; e.row_ptr = row_ptr; e.N = N;
+    }
     HGNN_TRY(launch_edge_bwd(st, H, bf16, e));
   }
   HGNN_TRY(stream_after(sx, st, ss.ev[2]));
@@ -445,7 +455,9 @@ static int32_t mp_layer_bwd_impl(void* stream, int32_t N, int64_t E, int32_t H, 
   else
     HGNN_TRY(launch_wgrad_frag(sx, H, bf16, E, s.a1_pk, w.gz2_pk, w.partial2, gW + o.W2));
   // g_P (and, on request, the gradient with respect to d2: the dot of every g_z1 row with the d2 row of W1)
-  if (k > 1) {
+  if (dsum_in_kernel) {
+    // g_P left the edge kernel already
+  } else if (k > 1) {
     // several attributes: the gradient with respect to them (on request) is a pass of its own over g_z1
     HGNN_TRY(launch_segsum_vm(st, H, bf16, N, row_ptr, nullptr, w.gz1_vm, w.g_PQ, 2 * H, PT_SEGSUM_DST));
     if (g_d2) HGNN_TRY(launch_gattr_vm(st, H, E, w.gz1_vm, W + o.W1 + 2 * HH, k, g_d2));

@@ -21,11 +21,15 @@ def _edges(rng, N, E):
     return row_ptr, dst, col, d2, rvec
 
 
-def _run_layer(N, E, H, dtype, seed):
+def _run_layer(N, E, H, dtype, seed, lengths=None):
     import torch
     from paper_2506_21788_amd import binding as B
     rng = np.random.default_rng(seed)
     row_ptr, dst, col, d2, rvec = _edges(rng, N, E)
+    if lengths is not None:   # chosen row lengths instead of random destinations
+        assert len(lengths) == N and sum(lengths) == E
+        dst = np.repeat(np.arange(N, dtype=np.int32), lengths)
+        row_ptr = np.concatenate([[0], np.cumsum(lengths)]).astype(np.int32)
     colT_ptr, permT = oracle.transpose_plan(col, N)
     W = init_layer_weights(rng, H).astype(np.float32)
     h = rng.standard_normal((N, H)).astype(np.float32)
@@ -108,6 +112,31 @@ def test_layer_without_saved_buffer_recomputes(H, dtype, N, E):
                                2 * 16384 + 97, 3 * 16384 - 1])
 def test_layer_bf16_pairs_edge_counts(E):
     _run_layer(N=700, E=E, H=256, dtype="bf16", seed=E + 1)
+
+
+# With bf16 pairs the reverse edge kernel sums g_z1 per destination out of its 64-edge tile, in 32-edge units: rows
+# inside one unit are written directly, rows that cross units are added from per-unit partials by a second kernel,
+# empty rows are zeroed there. Row lengths around the unit and tile sizes, at every alignment, with empty rows between.
+@pytest.mark.parametrize("pattern", ["mixed", "aligned", "long", "ones", "one_row", "tail_rows_empty"])
+def test_layer_bf16_pairs_row_lengths(pattern, monkeypatch):
+    rng = np.random.default_rng(7)
+    if pattern == "mixed":
+        lengths = [int(x) for x in rng.choice([0, 0, 1, 2, 5, 30, 31, 32, 33, 63, 64, 65, 96, 127, 129, 200], size=400)]
+    elif pattern == "aligned":
+        lengths = [32, 32, 64, 0, 32, 96, 0, 0, 64, 128, 32, 1, 31, 32] * 20
+    elif pattern == "long":
+        lengths = [700, 3, 0, 1025, 64, 5000, 1]
+    elif pattern == "ones":
+        lengths = [1] * 777
+    elif pattern == "one_row":
+        lengths = [0, 0, 4321, 0]
+    else:
+        lengths = [40, 17, 64, 7] + [0] * 50
+    N, E = len(lengths), sum(lengths)
+    _run_layer(N=N, E=E, H=256, dtype="bf16", seed=11, lengths=lengths)
+    # the separate pass over g_z1 (kept for the calls that ask for the gradient with respect to d2) gives the same
+    monkeypatch.setenv("HGNN_DSUM_IN_KERNEL", "0")
+    _run_layer(N=N, E=E, H=256, dtype="bf16", seed=11, lengths=lengths)
 
 
 @pytest.mark.parametrize("H,dtype,E", [(64, "f32", 1000), (64, "bf16", 4097), (128, "f32", 8191), (128, "bf16", 8193),
