@@ -77,7 +77,7 @@ struct EdgeBwdArgs {
   float* attrpart = nullptr;     // scratch: [splits][k][H] partial sums, edge_bwd_attrpart_floats()
   float* g_W1a = nullptr;        // out [k,H]
   // g_P[i,:] = sum of g_z1 over the edges of destination row i, formed inside the kernel from the tile's g_z1 in LDS
-  // (bf16 pairs, i.e. edge_pairs(), without edge attributes; null: not formed, the caller runs launch_segsum_vm).
+  // (where edge_bwd_sums_dst() holds, without edge attributes; null: not formed, the caller runs launch_segsum_vm).
   // A row that lies inside one 32-edge unit is written directly; the others leave one partial per unit in dpart
   // ([units][2][H]: slot 1 = the unit in which the row starts, slot 0 = every later unit) and a second small kernel
   // adds them in unit order and writes zeros for empty rows.
@@ -88,6 +88,8 @@ struct EdgeBwdArgs {
   int N = 0;
 };
 inline size_t edge_bwd_dpart_floats(int64_t E, int H) { return (size_t)((E + 31) / 32) * 2 * H; }
+// the operand types and widths for which k_edge_bwd can form g_P itself (an edge's g_z1 is 128 words there)
+inline bool edge_bwd_sums_dst(int H, bool bf16) { return edge_pairs(H, bf16) || (!bf16 && H == 128); }
 size_t edge_bwd_attrpart_floats(int H);
 size_t edge_bwd_colpart_floats(int H);
 int32_t launch_edge_bwd(hipStream_t st, int H, bool bf16, const EdgeBwdArgs& a);

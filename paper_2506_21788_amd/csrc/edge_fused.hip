@@ -1174,10 +1174,11 @@ __device__ __forceinline__ void edge_bwd_tile(const EdgeBwdArgs& p, unsigned cha
   const int g = lane >> 5, x = lane & 31;
   // byte offset of this lane's first column inside a row: word wc*32 + x of bf16 pairs, else column wc*CB*32 + x
   const unsigned colb = (unsigned)((PAIRS ? wc * 32 : wc * C::CB * 32) + x) * 4u;
-  static_assert(!DSUM || (PAIRS && !ATTR), "the in-kernel destination sums take bf16 pairs without attributes");
+  static_assert(!DSUM || ((PAIRS || (!BF16 && H == 128)) && !ATTR),
+                "the in-kernel destination sums take 128 words per edge (bf16 pairs at H = 256, fp32 at H = 128)");
   // DSUM: the last phase also leaves the tile's g_z1 words row-major in LDS (row pitch of the A tile, which is no
   // longer needed then); this lane writes word wc*32 + x of the rows 4g + (constant)
-  constexpr int DPITCH = C::STRIDE / 2;
+  constexpr int DPITCH = PAIRS ? C::STRIDE / 2 : C::STRIDE;
   unsigned* dsw = reinterpret_cast<unsigned*>(smem) + (4 * g) * DPITCH + wc * 32 + x;
   // the destinations of the edges next to the tile decide whether its first and last row are complete here
   int dprev = -1, dnext = -1;
@@ -1424,7 +1425,10 @@ __device__ __forceinline__ void edge_bwd_tile(const EdgeBwdArgs& p, unsigned cha
           } else {
             char* o = uoff(p.gz1_vm, blk * 4);
 #pragma unroll
-            for (int u = 0; u < 8; ++u) stg_nt<float>(o, lane * 4u + u * 256u, gv[j][u]);
+            for (int u = 0; u < 8; ++u) {
+              stg_nt<float>(o, lane * 4u + u * 256u, gv[j][u]);
+              if constexpr (DSUM) dsw[(rblk * 32 + 8 * (2 * vh + (u >> 2)) + (u & 3)) * DPITCH] = __float_as_uint(gv[j][u]);
+            }
           }
         }
       }
@@ -1433,7 +1437,7 @@ __device__ __forceinline__ void edge_bwd_tile(const EdgeBwdArgs& p, unsigned cha
     }
   }
   // ---- g_P: the tile's g_z1 words summed per destination out of LDS. The edges are sorted by destination, so a row
-  // is a run of consecutive edges. A thread owns one word (two columns) of one 32-edge half of the tile and adds the
+  // is a run of consecutive edges. A thread owns one word (two bf16 columns or one fp32 column) of one 32-edge half of the tile and adds the
   // half's edges in order; where the destination changes (the same place for every thread of a wavefront: scalar
   // branches on one ballot mask) the finished run goes to g_P when it is the whole row, otherwise to the half's partial
   // slot: slot 1 when the row starts in this half, slot 0 when it started earlier. k_dsum_fix adds a row's slots.
@@ -1460,8 +1464,12 @@ __device__ __forceinline__ void edge_bwd_tile(const EdgeBwdArgs& p, unsigned cha
       auto flush = [&](bool ef) {
         const int d = __builtin_amdgcn_readfirstlane(s[32 * hf + k0]);
         float* o = (sf && ef) ? p.gP + (size_t)d * p.ldgP : p.dpart + ((size_t)(ge0 >> 5) * 2 + (sf ? 1 : 0)) * H;
-        o[(w >> 5) * 64 + (w & 31)] = a0;
-        o[(w >> 5) * 64 + 32 + (w & 31)] = a1;
+        if constexpr (PAIRS) {
+          o[(w >> 5) * 64 + (w & 31)] = a0;
+          o[(w >> 5) * 64 + 32 + (w & 31)] = a1;
+        } else {
+          o[w] = a0;
+        }
       };
 #pragma unroll
       for (int k = 0; k < 32; ++k) {
@@ -1472,8 +1480,12 @@ __device__ __forceinline__ void edge_bwd_tile(const EdgeBwdArgs& p, unsigned cha
           sf = true;
         }
         if (FULL || k < nvalid) {
-          a0 += __uint_as_float(wd[k] << 16);
-          a1 += __uint_as_float(wd[k] & 0xffff0000u);
+          if constexpr (PAIRS) {
+            a0 += __uint_as_float(wd[k] << 16);
+            a1 += __uint_as_float(wd[k] & 0xffff0000u);
+          } else {
+            a0 += __uint_as_float(wd[k]);
+          }
         }
       }
       flush(ends);
@@ -1484,27 +1496,26 @@ __device__ __forceinline__ void edge_bwd_tile(const EdgeBwdArgs& p, unsigned cha
 
 // g_P rows that k_edge_bwd could not finish inside one 32-edge unit: the partial of the unit in which the row starts
 // (slot 1) plus the partials of the later units (slot 0), in unit order; empty rows are set to zero. One wavefront per
-// atom, four columns per lane.
+// atom, H/64 columns per lane.
 template <int H>
 __global__ void __launch_bounds__(256) k_dsum_fix(int N, const int32_t* __restrict__ row_ptr,
                                                    const float* __restrict__ dpart, float* __restrict__ gP, int ldgP) {
-  static_assert(H == 256, "four columns per lane");
+  static_assert(H == 256 || H == 128, "four or two columns per lane");
+  constexpr int V = H / 64;
+  typedef float vec_t __attribute__((ext_vector_type(V)));
   const int i = (int)(((size_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6);
   const int lane = threadIdx.x & 63;
   if (i >= N) return;
   const int ra = row_ptr[i], rb = row_ptr[i + 1];
-  float4* o = reinterpret_cast<float4*>(gP + (size_t)i * ldgP) + lane;
+  vec_t* o = reinterpret_cast<vec_t*>(gP + (size_t)i * ldgP) + lane;
   if (ra == rb) {
-    *o = make_float4(0.f, 0.f, 0.f, 0.f);
+    *o = vec_t(0.f);
     return;
   }
   const int u0 = ra >> 5, uk = (rb - 1) >> 5;
   if (u0 == uk) return;
-  float4 a = reinterpret_cast<const float4*>(dpart + ((size_t)u0 * 2 + 1) * H)[lane];
-  for (int u = u0 + 1; u <= uk; ++u) {
-    const float4 b = reinterpret_cast<const float4*>(dpart + (size_t)u * 2 * H)[lane];
-    a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
-  }
+  vec_t a = reinterpret_cast<const vec_t*>(dpart + ((size_t)u0 * 2 + 1) * H)[lane];
+  for (int u = u0 + 1; u <= uk; ++u) a += reinterpret_cast<const vec_t*>(dpart + (size_t)u * 2 * H)[lane];
   *o = a;
 }
 
@@ -1633,9 +1644,10 @@ int32_t launch_edge_bwd(hipStream_t st, int H, bool bf16, const EdgeBwdArgs& a) 
                (long long)a.E);
   HGNN_REQUIRE(a.ldgM == (edge_pairs(H, bf16) ? H / 2 : 2 * H), HGNN_ERR_BAD_SHAPE,
                "g_M must be the second half of a [N,2H] tensor, or [N,H/2] words of bf16 pairs");
-  HGNN_REQUIRE(!a.gP || (edge_pairs(H, bf16) && a.k <= 1 && a.dpart && a.row_ptr && a.N > 0 && a.ldgP >= H &&
+  HGNN_REQUIRE(!a.gP || (edge_bwd_sums_dst(H, bf16) && a.k <= 1 && a.dpart && a.row_ptr && a.N > 0 && a.ldgP >= H &&
                          a.ldgP % 4 == 0),
-               HGNN_ERR_BAD_SHAPE, "in-kernel destination sums: bf16 operands at H = 256 without edge attributes");
+               HGNN_ERR_BAD_SHAPE,
+               "in-kernel destination sums: bf16 operands at H = 256 or fp32 operands at H = 128, no edge attributes");
   if (a.k > 1) {
     HGNN_REQUIRE(bf16 && a.k <= ATTR_K && a.W1a && a.attrpart && a.g_W1a && (a.attr || a.E == 0), HGNN_ERR_BAD_SHAPE,
                  "edge attributes on the fused kernels: bf16 operands, 2 <= k <= %d", ATTR_K);
@@ -1648,7 +1660,9 @@ int32_t launch_edge_bwd(hipStream_t st, int H, bool bf16, const EdgeBwdArgs& a) 
   }
   switch (H) {
     case 64: return bf16 ? launch_edge_bwd_t<64, true, false>(st, a) : launch_edge_bwd_t<64, false, false>(st, a);
-    case 128: return bf16 ? launch_edge_bwd_t<128, true, false>(st, a) : launch_edge_bwd_t<128, false, false>(st, a);
+    case 128:
+      if (!bf16 && a.gP) return launch_edge_bwd_t<128, false, false, true>(st, a);
+      return bf16 ? launch_edge_bwd_t<128, true, false>(st, a) : launch_edge_bwd_t<128, false, false>(st, a);
     case 256:
       if (bf16 && a.gP) return launch_edge_bwd_t<256, true, false, true>(st, a);
       return bf16 ? launch_edge_bwd_t<256, true, false>(st, a) : launch_edge_bwd_t<256, false, false>(st, a);

@@ -102,7 +102,7 @@ static LayerWs carve_ws(void* p, int N, int64_t E, int H, bool bf16, int k = 1) 
   w.partial3 = c.take<float>(wgrad_partial_floats(H, N, 5, 1));   // the layer's five atom-level blocks in one launch
   w.cs_partial = c.take<float>(wgrad_colsum_partial_floats(H, N));
   w.attrpart = k > 1 ? c.take<float>(edge_bwd_attrpart_floats(H)) : nullptr;
-  w.dpart = edge_pairs(H, bf16) && k <= 1 ? c.take<float>(edge_bwd_dpart_floats(E, H)) : nullptr;
+  w.dpart = edge_bwd_sums_dst(H, bf16) && k <= 1 ? c.take<float>(edge_bwd_dpart_floats(E, H)) : nullptr;
   w.bytes = c.used();
   return w;
 }
@@ -415,11 +415,11 @@ static int32_t mp_layer_bwd_impl(void* stream, int32_t N, int64_t E, int32_t H, 
   // every CU by itself, so the side stream is drained first instead of competing with it.
   HGNN_TRY(launch_edge_cvec(st, E, dst, rvec, g_v_out, alpha, w.cvec));
   HGNN_TRY(stream_after(st, sx, ss.ev[5]));
-  // With bf16 pairs the reverse edge kernel also sums g_z1 per destination (out of the tile it holds in LDS), unless
+  // With bf16 pairs, or fp32 operands at H = 128, the reverse edge kernel also sums g_z1 per destination (out of the tile it holds in LDS), unless
   // the gradient with respect to d2 is asked for, which the separate pass over g_z1 forms on its way.
   // HGNN_DSUM_IN_KERNEL=0 keeps the separate pass (for comparing the two).
   const char* dsum_env = getenv("HGNN_DSUM_IN_KERNEL");
-  const bool dsum_in_kernel = edge_pairs(H, bf16) && k <= 1 && !g_d2 && N > 0 && !(dsum_env && dsum_env[0] == '0');
+  const bool dsum_in_kernel = edge_bwd_sums_dst(H, bf16) && k <= 1 && !g_d2 && N > 0 && !(dsum_env && dsum_env[0] == '0');
   {
     EdgeBwdArgs e;
     e.E = E; e.dst = dst; e.col = col;

@@ -114,11 +114,13 @@ def test_layer_bf16_pairs_edge_counts(E):
     _run_layer(N=700, E=E, H=256, dtype="bf16", seed=E + 1)
 
 
-# With bf16 pairs the reverse edge kernel sums g_z1 per destination out of its 64-edge tile, in 32-edge units: rows
+# With bf16 pairs (H = 256) and with fp32 operands at H = 128 the reverse edge kernel sums g_z1 per destination out of
+# its 64-edge tile, in 32-edge units: rows
 # inside one unit are written directly, rows that cross units are added from per-unit partials by a second kernel,
 # empty rows are zeroed there. Row lengths around the unit and tile sizes, at every alignment, with empty rows between.
+@pytest.mark.parametrize("H,dtype", [(256, "bf16"), (128, "f32")])
 @pytest.mark.parametrize("pattern", ["mixed", "aligned", "long", "ones", "one_row", "tail_rows_empty"])
-def test_layer_bf16_pairs_row_lengths(pattern, monkeypatch):
+def test_layer_row_lengths_with_destination_sums_in_the_edge_kernel(pattern, H, dtype, monkeypatch):
     rng = np.random.default_rng(7)
     if pattern == "mixed":
         lengths = [int(x) for x in rng.choice([0, 0, 1, 2, 5, 30, 31, 32, 33, 63, 64, 65, 96, 127, 129, 200], size=400)]
@@ -133,10 +135,10 @@ def test_layer_bf16_pairs_row_lengths(pattern, monkeypatch):
     else:
         lengths = [40, 17, 64, 7] + [0] * 50
     N, E = len(lengths), sum(lengths)
-    _run_layer(N=N, E=E, H=256, dtype="bf16", seed=11, lengths=lengths)
+    _run_layer(N=N, E=E, H=H, dtype=dtype, seed=11, lengths=lengths)
     # the separate pass over g_z1 (kept for the calls that ask for the gradient with respect to d2) gives the same
     monkeypatch.setenv("HGNN_DSUM_IN_KERNEL", "0")
-    _run_layer(N=N, E=E, H=256, dtype="bf16", seed=11, lengths=lengths)
+    _run_layer(N=N, E=E, H=H, dtype=dtype, seed=11, lengths=lengths)
 
 
 @pytest.mark.parametrize("H,dtype,E", [(64, "f32", 1000), (64, "bf16", 4097), (128, "f32", 8191), (128, "bf16", 8193),
