@@ -21,7 +21,7 @@ PEAK_HBM_GBS = 8000.0
 PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
 
 
-def kernel_work(tag, N, E, H, dtype):
+def kernel_work(tag, N, E, H, dtype, dsum_in_edge_kernel=False):
     """Algorithmic work of ONE launch of a kernel class: (flops on the matrix cores, HBM bytes).
 
     Bytes are what the method has to move for that kernel: every edge tensor it streams once (b bytes
@@ -34,7 +34,8 @@ def kernel_work(tag, N, E, H, dtype):
     if tag == "edge_fused_fwd":      # out: z2 (and a1 unless recomputed); in: dst, col, d2; gathers P|Q
         return 2.0 * EH * H, (1 if pairs else 2) * EH * b + 12.0 * E + 2 * NH * b
     if tag == "edge_fused_bwd":      # in: z2, dst, col, d2, c; out: g_z2, g_z1; gathers P|Q, g_M
-        return 4.0 * EH * H, 3 * EH * b + 16.0 * E + 3 * NH * b
+        # where the kernel also sums g_z1 per destination (no separate pass over g_z1 for that): out g_P as well
+        return 4.0 * EH * H, 3 * EH * b + 16.0 * E + 3 * NH * b + (NH * 4 if dsum_in_edge_kernel else 0.0)
     if tag == "wgrad_edge":          # in: g_z2 and a1 (or dst, col, d2 and gathers of P|Q to recompute a1); out: H x H
         if pairs:
             return 2.0 * EH * H, EH * b + 12.0 * E + 2 * NH * b + 4.0 * H * H
@@ -42,6 +43,8 @@ def kernel_work(tag, N, E, H, dtype):
     if tag == "seg_fwd":             # in: z2, rvec, row_ptr; out: M, v
         return 0.0, EH * b + 12.0 * E + 4.0 * (N + 1) + (NH + 6.0 * N) * 4
     if tag in ("segsum_dst", "segsum_src"):
+        # (where the edge kernel forms the destination sums, the source-sorted launch also adds the per-unit partials
+        # of the rows that cross units: not algorithmic bytes)
         return 0.0, EH * b + 4.0 * (N + 1) + NH * 4 + (4.0 * E if tag == "segsum_src" else 0.0)
     if tag == "gemm_node":           # one H x H block product per atom row, fp32 in / out
         return 2.0 * NH * H, 2 * NH * 4
@@ -63,8 +66,8 @@ def kernel_work(tag, N, E, H, dtype):
     return 0.0, 0.0
 
 
-def roofline_of(tag, avg_s, N, E, H, dtype, traffic=None):
-    flops, nbytes = kernel_work(tag, N, E, H, dtype)
+def roofline_of(tag, avg_s, N, E, H, dtype, traffic=None, dsum_in_edge_kernel=False):
+    flops, nbytes = kernel_work(tag, N, E, H, dtype, dsum_in_edge_kernel)
     mfma_dtype = dtype
     if dtype == "f32" and tag in ("edge_fused_fwd", "edge_fused_bwd", "wgrad_edge"):
         # fp32 operands of the per-edge products are split into three bf16 terms each: six bf16 products on the
@@ -212,7 +215,9 @@ def measure(name, steps, warmup, rbf=0, move=False, pos_grad=False, hip_graph=Fa
     t_mp = (time.perf_counter() - t0) / steps
 
     avg_s = dom_ms / max(dom_n, 1) * 1e-3
-    roofline = roofline_of(dom, avg_s, N, E, H, hp["dtype"], read_traffic(name, dom))
+    # no launch of the destination-sorted sum in the split <=> the reverse edge kernel formed those sums itself
+    dsum = "segsum_dst" not in split and "edge_fused_bwd" in split
+    roofline = roofline_of(dom, avg_s, N, E, H, hp["dtype"], read_traffic(name, dom), dsum)
     roofline["launches_per_step"] = dom_n / steps
     if roofline["traffic"] is not None:
         roofline["traffic_source"] = (f"profiles/traffic_{name}.txt: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of this "
@@ -275,7 +280,7 @@ def print_breakdown(name, m):
     print(f"--- {name}: {m['ms_per_step']:.3f} ms/step", file=sys.stderr)
     for k, v in sorted(m["_split"].items(), key=lambda kv: -kv[1]["ms_per_step"]):
         per = v["ms_per_step"] / v["launches_per_step"] * 1e-3
-        r = roofline_of(k, per, N, E, H, m["dtype"])
+        r = roofline_of(k, per, N, E, H, m["dtype"], None, "segsum_dst" not in m["_split"])
         print(f"{k:18s} {v['launches_per_step']:6.1f} launches  {v['ms_per_step']:9.3f} ms/step  "
               f"{r['achieved']:10.1f} {r['unit']:8s} {100 * r['frac']:5.1f} % of {r['bound']} peak", file=sys.stderr)
 

@@ -51,6 +51,14 @@ int32_t launch_seg_fwd_vm(hipStream_t st, int H, bool bf16, int N, const int32_t
                           const float* rvec, const float* wx, float alpha, const float* v_in, float* M,
                           float* v_out, float* xe = nullptr);
 
+// what finishes the rows of g_P that the reverse edge kernel left as per-unit partials (see EdgeBwdArgs::gP)
+struct DsumFix {
+  const int32_t* row_ptr;
+  const float* dpart;
+  float* gP;       // null: nothing to finish
+  int ldgP;
+};
+
 struct EdgeBwdArgs {
   int64_t E;
   const int32_t *dst, *col;
@@ -78,16 +86,24 @@ struct EdgeBwdArgs {
   float* g_W1a = nullptr;        // out [k,H]
   // g_P[i,:] = sum of g_z1 over the edges of destination row i, formed inside the kernel from the tile's g_z1 in LDS
   // (where edge_bwd_sums_dst() holds, without edge attributes; null: not formed, the caller runs launch_segsum_vm).
-  // A row that lies inside one 32-edge unit is written directly; the others leave one partial per unit in dpart
-  // ([units][2][H]: slot 1 = the unit in which the row starts, slot 0 = every later unit) and a second small kernel
-  // adds them in unit order and writes zeros for empty rows.
+  // A row that lies inside one unit of DSUM_UNIT edges is written directly; the others leave one partial per unit in dpart
+  // ([units][2][H]: slot 1 = the unit in which the row starts, slot 0 = every later unit); edge_bwd_dsum_fix() below
+  // names what adds them in unit order and writes zeros for empty rows.
   float* gP = nullptr;           // out [N, ldgP]
   int ldgP = 0;
   float* dpart = nullptr;        // scratch: edge_bwd_dpart_floats(E, H)
   const int32_t* row_ptr = nullptr;   // [N+1], the rows of dst
   int N = 0;
 };
-inline size_t edge_bwd_dpart_floats(int64_t E, int H) { return (size_t)((E + 31) / 32) * 2 * H; }
+// The caller passes this to the launch_segsum_vm call that follows (the source-sorted sum: one wavefront per atom as
+// well), which adds the partials on its way; a launch of its own for that would cost about 20 us.
+inline DsumFix edge_bwd_dsum_fix(const EdgeBwdArgs& a) { return DsumFix{a.row_ptr, a.dpart, a.gP, a.ldgP}; }
+// edges per unit of those sums: half of the kernel's 64-edge tile, so that all four wavefronts walk. With the whole
+// tile as the unit fewer rows cross units and the partials are half the bytes, but only two wavefronts walk, twice
+// as long: measured 0.12 ms per step slower in the edge kernel for 0.05 ms gained in the sum that adds the partials
+// (config 4), and the same sign on config 5.
+constexpr int DSUM_UNIT = 32;
+inline size_t edge_bwd_dpart_floats(int64_t E, int H) { return (size_t)((E + DSUM_UNIT - 1) / DSUM_UNIT) * 2 * H; }
 // the operand types and widths for which k_edge_bwd can form g_P itself (an edge's g_z1 is 128 words there)
 inline bool edge_bwd_sums_dst(int H, bool bf16) { return edge_pairs(H, bf16) || (!bf16 && H == 128); }
 size_t edge_bwd_attrpart_floats(int H);
@@ -116,10 +132,11 @@ int32_t launch_wgrad_frag_recompute32(hipStream_t st, int H, int64_t E, const in
 
 // out[i, 0..H) (row pitch ldo) = sum over t in ptr[i]:ptr[i+1] of X[perm ? perm[t] : t, :], X v-major (bf16 or
 // fp32), accumulated in fp32
+// fix (optional): wavefront i also finishes row i of the g_P that the reverse edge kernel started (H = 128 or 256)
 // dot (optional): [E] out, dot[e] = sum_c wdot[c] X[e][c] for every edge of the list
 int32_t launch_segsum_vm(hipStream_t st, int H, bool bf16, int N, const int32_t* ptr, const int32_t* perm,
                          const void* X_vm, float* out, int ldo, int tag, const float* wdot = nullptr,
-                         float* dot = nullptr);
+                         float* dot = nullptr, const DsumFix* fix = nullptr);
 
 // g_attr[e][j] = sum_c X[e][c] W1a[j][c] for every edge (X = g_z1, v-major bf16; 2 <= k <= 16): the gradient with
 // respect to k > 1 edge attributes, for callers that ask for it

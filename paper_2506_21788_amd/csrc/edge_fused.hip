@@ -930,12 +930,50 @@ int32_t launch_seg_fwd_vm(hipStream_t st, int H, bool bf16, int N, const int32_t
   return HGNN_OK;
 }
 
+// g_P rows that k_edge_bwd could not finish inside one unit of DSUM_UNIT edges (see EdgeBwdArgs::gP): the partial of the unit in
+// which row i starts (slot 1) plus the partials of the later units (slot 0), in unit order; an empty row is set to
+// zero. One wavefront per atom, H/64 columns per lane. In two steps, so that the loads of the first four partials
+// travel while the wavefront does its other work.
+template <int H>
+struct DsumFixRow {
+  static_assert(H % 64 == 0, "whole columns per lane");
+  typedef float vec_t __attribute__((ext_vector_type(H / 64)));
+  static constexpr int AHEAD = 4;
+  vec_t p[AHEAD];
+  int ra, rb, u0, uk;
+  __device__ __forceinline__ void issue(int i, int lane, const DsumFix& f) {
+    ra = f.row_ptr[i];
+    rb = f.row_ptr[i + 1];
+    u0 = ra / DSUM_UNIT;
+    uk = rb > ra ? (rb - 1) / DSUM_UNIT : u0;
+#pragma unroll
+    for (int q = 0; q < AHEAD; ++q) {
+      p[q] = vec_t(0.f);
+      if (u0 < uk && u0 + q <= uk)
+        p[q] = reinterpret_cast<const vec_t*>(f.dpart + ((size_t)(u0 + q) * 2 + (q == 0 ? 1 : 0)) * H)[lane];
+    }
+  }
+  __device__ __forceinline__ void finish(int i, int lane, const DsumFix& f) const {
+    vec_t* o = reinterpret_cast<vec_t*>(f.gP + (size_t)i * f.ldgP) + lane;
+    if (ra == rb) {
+      *o = vec_t(0.f);
+      return;
+    }
+    if (u0 == uk) return;
+    vec_t a = p[0];
+#pragma unroll
+    for (int q = 1; q < AHEAD; ++q) a += p[q];   // units beyond the row's last one hold zeros here
+    for (int u = u0 + AHEAD; u <= uk; ++u) a += reinterpret_cast<const vec_t*>(f.dpart + (size_t)u * 2 * H)[lane];
+    *o = a;
+  }
+};
+
 // DOT: also dot[e] = sum_c wdot[c] X[e][c] for every edge of the list (the gradient with respect to d2 when X = g_z1
 // and wdot is the row of W1 that acts on d2)
 template <int H, bool BF16, bool DOT>
 __global__ void __launch_bounds__(256)
 k_segsum_vm(int N, const int32_t* __restrict__ ptr, const int32_t* __restrict__ perm, const void* __restrict__ X,
-            float* __restrict__ out, int ldo, const float* __restrict__ wdot, float* __restrict__ dot) {
+            float* __restrict__ out, int ldo, const float* __restrict__ wdot, float* __restrict__ dot, DsumFix fix) {
   using S = SegCols<H, BF16, BF16 && H == 256>;
   constexpr int NV = S::NPASS * S::PER;
   const int i = __builtin_amdgcn_readfirstlane((int)(((size_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6));
@@ -943,6 +981,9 @@ k_segsum_vm(int N, const int32_t* __restrict__ ptr, const int32_t* __restrict__ 
   if (i >= N) return;
   const int hp = lane >> 5, x = lane & 31;
   const int t0 = ptr[i], t1 = ptr[i + 1];
+  // on request this wavefront also finishes atom i's row of another sum, the one the reverse edge kernel started
+  DsumFixRow<H> fr;
+  if (fix.gP) fr.issue(i, lane, fix);
   if constexpr (DOT) {
     float acc[NV], wl[NV];
 #pragma unroll
@@ -980,6 +1021,7 @@ k_segsum_vm(int N, const int32_t* __restrict__ ptr, const int32_t* __restrict__ 
     for (int c = 0; c < S::NPASS; ++c)
 #pragma unroll
       for (int k = 0; k < S::PER; ++k) out[(size_t)i * ldo + S::column(c, hp, x, k)] = acc[c * S::PER + k];
+    if (fix.gP) fr.finish(i, lane, fix);
     return;
   }
   float acc[NV];
@@ -1013,16 +1055,19 @@ k_segsum_vm(int N, const int32_t* __restrict__ ptr, const int32_t* __restrict__ 
   for (int c = 0; c < S::NPASS; ++c)
 #pragma unroll
     for (int k = 0; k < S::PER; ++k) out[(size_t)i * ldo + S::column(c, hp, x, k)] = acc[c * S::PER + k];
+  if (fix.gP) fr.finish(i, lane, fix);
 }
 
 int32_t launch_segsum_vm(hipStream_t st, int H, bool bf16, int N, const int32_t* ptr, const int32_t* perm,
-                         const void* X_vm, float* out, int ldo, int tag, const float* wdot, float* dot) {
+                         const void* X_vm, float* out, int ldo, int tag, const float* wdot, float* dot,
+                         const DsumFix* fix) {
   if (N <= 0) return HGNN_OK;
+  const DsumFix fx = fix ? *fix : DsumFix{nullptr, nullptr, nullptr, 0};
   const unsigned grid = (unsigned)(((int64_t)N * 64 + 255) / 256);
   ProfScope ps(tag, st);
 #define HGNN_SEGS(HH, BB)                                                                            \
-  if (dot) k_segsum_vm<HH, BB, true><<<grid, 256, 0, st>>>(N, ptr, perm, X_vm, out, ldo, wdot, dot); \
-  else k_segsum_vm<HH, BB, false><<<grid, 256, 0, st>>>(N, ptr, perm, X_vm, out, ldo, wdot, dot)
+  if (dot) k_segsum_vm<HH, BB, true><<<grid, 256, 0, st>>>(N, ptr, perm, X_vm, out, ldo, wdot, dot, fx); \
+  else k_segsum_vm<HH, BB, false><<<grid, 256, 0, st>>>(N, ptr, perm, X_vm, out, ldo, wdot, dot, fx)
   switch (H) {
     case 64: if (bf16) { HGNN_SEGS(64, true); } else { HGNN_SEGS(64, false); } break;
     case 128: if (bf16) { HGNN_SEGS(128, true); } else { HGNN_SEGS(128, false); } break;
@@ -1437,33 +1482,35 @@ __device__ __forceinline__ void edge_bwd_tile(const EdgeBwdArgs& p, unsigned cha
     }
   }
   // ---- g_P: the tile's g_z1 words summed per destination out of LDS. The edges are sorted by destination, so a row
-  // is a run of consecutive edges. A thread owns one word (two bf16 columns or one fp32 column) of one 32-edge half of the tile and adds the
-  // half's edges in order; where the destination changes (the same place for every thread of a wavefront: scalar
-  // branches on one ballot mask) the finished run goes to g_P when it is the whole row, otherwise to the half's partial
-  // slot: slot 1 when the row starts in this half, slot 0 when it started earlier. k_dsum_fix adds a row's slots.
+  // is a run of consecutive edges. A thread owns one word (two bf16 columns or one fp32 column) of one unit of the
+  // tile (DSUM_UNIT edges: half a tile, so two wavefronts per unit) and adds the unit's edges in order;
+  // where the destination changes (the same place for every thread of a wavefront: scalar branches on one ballot
+  // mask) the finished run goes to g_P when it is the whole row, otherwise to the unit's partial slot: slot 1 when
+  // the row starts in this unit, slot 0 when it started earlier. DsumFixRow adds a row's slots.
   if constexpr (DSUM) {
     __syncthreads();
+    constexpr int DU = DSUM_UNIT, NU = C::TM / DU;   // edges per unit, units per tile
     const unsigned* gw = reinterpret_cast<const unsigned*>(smem);
-    const int hf = __builtin_amdgcn_readfirstlane(tid >> 7);
+    const int hf = __builtin_amdgcn_readfirstlane(tid >> 7);   // the unit of the tile that this wavefront walks
     const int w = tid & 127;
     const int dl = s[lane];
     const int dq = s[lane ? lane - 1 : 0];
     const unsigned long long starts = __ballot(dl != (lane ? dq : dprev));   // bit r: edge r of the tile starts a row
-    const int ge0 = tile * C::TM + 32 * hf;
-    const int nvalid = FULL ? 32 : (E - ge0 < 32 ? E - ge0 : 32);
-    if (FULL || nvalid > 0) {
-      unsigned wd[32];
+    const int ge0 = tile * C::TM + DU * hf;
+    const int nvalid = FULL ? DU : (E - ge0 < DU ? E - ge0 : DU);
+    if (hf < NU && (FULL || nvalid > 0)) {
+      unsigned wd[DU];
 #pragma unroll
-      for (int k = 0; k < 32; ++k) wd[k] = (FULL || k < nvalid) ? gw[(32 * hf + k) * DPITCH + w] : 0u;
-      const unsigned m32 = (unsigned)(starts >> (32 * hf));
-      const bool ends = ge0 + 32 >= E ||
-                        (hf == 0 ? ((starts >> 32) & 1ull) != 0ull : dnext != __builtin_amdgcn_readfirstlane(s[63]));
+      for (int k = 0; k < DU; ++k) wd[k] = (FULL || k < nvalid) ? gw[(DU * hf + k) * DPITCH + w] : 0u;
+      const unsigned long long mu = starts >> (DU * hf);
+      const bool ends = ge0 + DU >= E || (hf == NU - 1 ? dnext != __builtin_amdgcn_readfirstlane(s[C::TM - 1])
+                                                       : ((starts >> ((DU * (hf + 1)) & 63)) & 1ull) != 0ull);
       float a0 = 0.f, a1 = 0.f;
       int k0 = 0;
-      bool sf = (m32 & 1u) != 0u;   // the run at hand starts its row
+      bool sf = (mu & 1ull) != 0ull;   // the run at hand starts its row
       auto flush = [&](bool ef) {
-        const int d = __builtin_amdgcn_readfirstlane(s[32 * hf + k0]);
-        float* o = (sf && ef) ? p.gP + (size_t)d * p.ldgP : p.dpart + ((size_t)(ge0 >> 5) * 2 + (sf ? 1 : 0)) * H;
+        const int d = __builtin_amdgcn_readfirstlane(s[DU * hf + k0]);
+        float* o = (sf && ef) ? p.gP + (size_t)d * p.ldgP : p.dpart + ((size_t)(ge0 / DU) * 2 + (sf ? 1 : 0)) * H;
         if constexpr (PAIRS) {
           o[(w >> 5) * 64 + (w & 31)] = a0;
           o[(w >> 5) * 64 + 32 + (w & 31)] = a1;
@@ -1472,8 +1519,8 @@ __device__ __forceinline__ void edge_bwd_tile(const EdgeBwdArgs& p, unsigned cha
         }
       };
 #pragma unroll
-      for (int k = 0; k < 32; ++k) {
-        if (k > 0 && ((m32 >> k) & 1u) && (FULL || k < nvalid)) {
+      for (int k = 0; k < DU; ++k) {
+        if (__builtin_expect(k > 0 && ((mu >> k) & 1ull) && (FULL || k < nvalid), 0)) {   // about one edge in thirty
           flush(true);
           a0 = a1 = 0.f;
           k0 = k;
@@ -1492,31 +1539,6 @@ __device__ __forceinline__ void edge_bwd_tile(const EdgeBwdArgs& p, unsigned cha
     }
     __syncthreads();   // the next tile's first phase writes the A tile again
   }
-}
-
-// g_P rows that k_edge_bwd could not finish inside one 32-edge unit: the partial of the unit in which the row starts
-// (slot 1) plus the partials of the later units (slot 0), in unit order; empty rows are set to zero. One wavefront per
-// atom, H/64 columns per lane.
-template <int H>
-__global__ void __launch_bounds__(256) k_dsum_fix(int N, const int32_t* __restrict__ row_ptr,
-                                                   const float* __restrict__ dpart, float* __restrict__ gP, int ldgP) {
-  static_assert(H == 256 || H == 128, "four or two columns per lane");
-  constexpr int V = H / 64;
-  typedef float vec_t __attribute__((ext_vector_type(V)));
-  const int i = (int)(((size_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6);
-  const int lane = threadIdx.x & 63;
-  if (i >= N) return;
-  const int ra = row_ptr[i], rb = row_ptr[i + 1];
-  vec_t* o = reinterpret_cast<vec_t*>(gP + (size_t)i * ldgP) + lane;
-  if (ra == rb) {
-    *o = vec_t(0.f);
-    return;
-  }
-  const int u0 = ra >> 5, uk = (rb - 1) >> 5;
-  if (u0 == uk) return;
-  vec_t a = reinterpret_cast<const vec_t*>(dpart + ((size_t)u0 * 2 + 1) * H)[lane];
-  for (int u = u0 + 1; u <= uk; ++u) a += reinterpret_cast<const vec_t*>(dpart + (size_t)u * 2 * H)[lane];
-  *o = a;
 }
 
 template <int H, bool BF16, bool ATTR, bool DSUM>
@@ -1624,11 +1646,6 @@ static int32_t launch_edge_bwd_t(hipStream_t st, const EdgeBwdArgs& a) {
     ProfScope ps(PT_EDGE_FUSED_BWD, st);
     k_edge_bwd<H, BF16, ATTR, DSUM><<<dim3((unsigned)grid), 256, lds, st>>>(a, (int)ntiles);
     HGNN_LAUNCH_CHECK("k_edge_bwd");
-  }
-  if constexpr (DSUM) {
-    ProfScope ps(PT_SEGSUM_DST, st);
-    k_dsum_fix<H><<<dim3((unsigned)(((int64_t)a.N * 64 + 255) / 256)), 256, 0, st>>>(a.N, a.row_ptr, a.dpart, a.gP, a.ldgP);
-    HGNN_LAUNCH_CHECK("k_dsum_fix");
   }
   float* dest[4] = {a.g_b2, a.g_wx, a.g_w1d, nullptr};
   HGNN_TRY(launch_reduce_partials(st, a.colpart, (int)grid * C::WR, 3, H, dest, 1, 0));

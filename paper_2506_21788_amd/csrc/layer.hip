@@ -419,6 +419,7 @@ static int32_t mp_layer_bwd_impl(void* stream, int32_t N, int64_t E, int32_t H, 
   // the gradient with respect to d2 is asked for, which the separate pass over g_z1 forms on its way.
   // HGNN_DSUM_IN_KERNEL=0 keeps the separate pass (for comparing the two).
   const char* dsum_env = getenv("HGNN_DSUM_IN_KERNEL");
+  DsumFix dfix{nullptr, nullptr, nullptr, 0};
   const bool dsum_in_kernel = edge_bwd_sums_dst(H, bf16) && k <= 1 && !g_d2 && N > 0 && !(dsum_env && dsum_env[0] == '0');
   {
     EdgeBwdArgs e;
@@ -441,6 +442,7 @@ static int32_t mp_layer_bwd_impl(void* stream, int32_t N, int64_t E, int32_t H, 
     e.g_b2 = gW + o.b2; e.g_wx = gW + o.wx; e.g_w1d = k > 1 ? nullptr : gW + o.W1 + 2 * HH;
     if (dsum_in_kernel) {
       e.gP = w.g_PQ; e.ldgP = 2 * H; e.dpart = w.dpart; e.row_ptr = row_ptr; e.N = N;
+      dfix = edge_bwd_dsum_fix(e);   // the source-sorted sum below adds the partials on its way
     }
     HGNN_TRY(launch_edge_bwd(st, H, bf16, e));
   }
@@ -466,7 +468,8 @@ static int32_t mp_layer_bwd_impl(void* stream, int32_t N, int64_t E, int32_t H, 
                               W + o.W1 + 2 * HH, g_d2));
   }
   if (g_rvec) HGNN_TRY(launch_edge_grvec(st, E, dst, s.xe, g_v_out, alpha, g_rvec));
-  HGNN_TRY(launch_segsum_vm(st, H, bf16, N, colT_ptr, permT, w.gz1_vm, w.g_PQ + H, 2 * H, PT_SEGSUM_SRC));  // g_Q
+  HGNN_TRY(launch_segsum_vm(st, H, bf16, N, colT_ptr, permT, w.gz1_vm, w.g_PQ + H, 2 * H, PT_SEGSUM_SRC, nullptr, nullptr,
+                            dsum_in_kernel ? &dfix : nullptr));  // g_Q
   {  // g_h = (g_h' + g_h(a)) + g_P W1a^T + g_Q W1b^T
     GemmArgs g;
     g.A[0] = w.g_PQ; g.lda[0] = 2 * H; g.A[1] = w.g_PQ + H; g.lda[1] = 2 * H; g.nkc = 2;
