@@ -98,11 +98,10 @@ struct EdgeBwdArgs {
 // The caller passes this to the launch_segsum_vm call that follows (the source-sorted sum: one wavefront per atom as
 // well), which adds the partials on its way; a launch of its own for that would cost about 20 us.
 inline DsumFix edge_bwd_dsum_fix(const EdgeBwdArgs& a) { return DsumFix{a.row_ptr, a.dpart, a.gP, a.ldgP}; }
-// edges per unit of those sums: half of the kernel's 64-edge tile, so that all four wavefronts walk. With the whole
-// tile as the unit fewer rows cross units and the partials are half the bytes, but only two wavefronts walk, twice
-// as long: measured 0.12 ms per step slower in the edge kernel for 0.05 ms gained in the sum that adds the partials
-// (config 4), and the same sign on config 5.
-constexpr int DSUM_UNIT = 32;
+// edges per unit of those sums: the kernel's 64-edge tile. Its two halves are walked by two wavefronts each and the
+// row that crosses the middle is put together inside the workgroup, so partials only arise at tile borders (with
+// 32-edge units nearly every row of 30 edges left partials: 160 MB of traffic per layer on config 4).
+constexpr int DSUM_UNIT = 64;
 inline size_t edge_bwd_dpart_floats(int64_t E, int H) { return (size_t)((E + DSUM_UNIT - 1) / DSUM_UNIT) * 2 * H; }
 // the operand types and widths for which k_edge_bwd can form g_P itself (an edge's g_z1 is 128 words there)
 inline bool edge_bwd_sums_dst(int H, bool bf16) { return edge_pairs(H, bf16) || (!bf16 && H == 128); }

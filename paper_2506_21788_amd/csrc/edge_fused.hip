@@ -1482,49 +1482,70 @@ __device__ __forceinline__ void edge_bwd_tile(const EdgeBwdArgs& p, unsigned cha
     }
   }
   // ---- g_P: the tile's g_z1 words summed per destination out of LDS. The edges are sorted by destination, so a row
-  // is a run of consecutive edges. A thread owns one word (two bf16 columns or one fp32 column) of one unit of the
-  // tile (DSUM_UNIT edges: half a tile, so two wavefronts per unit) and adds the unit's edges in order;
-  // where the destination changes (the same place for every thread of a wavefront: scalar branches on one ballot
-  // mask) the finished run goes to g_P when it is the whole row, otherwise to the unit's partial slot: slot 1 when
-  // the row starts in this unit, slot 0 when it started earlier. DsumFixRow adds a row's slots.
+  // is a run of consecutive edges. A thread owns one word (two bf16 columns or one fp32 column) of one of the
+  // tile's two halves of 32 edges and adds the half's edges in order; where the destination changes (the same place
+  // for every thread of a wavefront: scalar branches on one ballot mask) the finished run goes to g_P when it is the
+  // whole row, otherwise to the tile's partial slot: slot 1 when the row starts in this tile, slot 0 when it
+  // started earlier. DsumFixRow adds a row's slots.
   if constexpr (DSUM) {
+    static_assert(C::TM == 64 && DSUM_UNIT == C::TM, "one partial unit per tile, walked as two halves of 32 edges");
     __syncthreads();
-    constexpr int DU = DSUM_UNIT, NU = C::TM / DU;   // edges per unit, units per tile
     const unsigned* gw = reinterpret_cast<const unsigned*>(smem);
-    const int hf = __builtin_amdgcn_readfirstlane(tid >> 7);   // the unit of the tile that this wavefront walks
+    float2* carry = reinterpret_cast<float2*>(smem + C::LDS_BYTES + 8 * C::TM * 4);   // [128], see below
+    const int hf = __builtin_amdgcn_readfirstlane(tid >> 7);   // the half of the tile that this wavefront walks
     const int w = tid & 127;
     const int dl = s[lane];
     const int dq = s[lane ? lane - 1 : 0];
     const unsigned long long starts = __ballot(dl != (lane ? dq : dprev));   // bit r: edge r of the tile starts a row
-    const int ge0 = tile * C::TM + DU * hf;
-    const int nvalid = FULL ? DU : (E - ge0 < DU ? E - ge0 : DU);
-    if (hf < NU && (FULL || nvalid > 0)) {
-      unsigned wd[DU];
+    const int t0e = tile * C::TM;
+    const int ge0 = t0e + 32 * hf;
+    const int nvalid = FULL ? 32 : (E - ge0 < 32 ? E - ge0 : 32);
+    // a finished run goes to g_P when it is its whole row, else to the tile's partial slot (1: the row starts in
+    // this tile, 0: it started earlier)
+    auto put = [&](bool sf, bool ef, int d, float v0, float v1) {
+      float* o = (sf && ef) ? p.gP + (size_t)d * p.ldgP : p.dpart + ((size_t)tile * 2 + (sf ? 1 : 0)) * H;
+      if constexpr (PAIRS) {
+        o[(w >> 5) * 64 + (w & 31)] = v0;
+        o[(w >> 5) * 64 + 32 + (w & 31)] = v1;
+      } else {
+        o[w] = v0;
+      }
+    };
+    // the row that crosses the middle of the tile is summed by both halves: the first half hands its part over in
+    // LDS, the second half keeps its own part in registers and finishes the row behind the barrier below
+    const bool cont = (FULL || t0e + 32 < E) && ((starts >> 32) & 1ull) == 0ull;
+    float c0 = 0.f, c1 = 0.f;
+    int cd = 0;
+    bool cef = false;
+    if (FULL || nvalid > 0) {
+      unsigned wd[32];
 #pragma unroll
-      for (int k = 0; k < DU; ++k) wd[k] = (FULL || k < nvalid) ? gw[(DU * hf + k) * DPITCH + w] : 0u;
-      const unsigned long long mu = starts >> (DU * hf);
-      const bool ends = ge0 + DU >= E || (hf == NU - 1 ? dnext != __builtin_amdgcn_readfirstlane(s[C::TM - 1])
-                                                       : ((starts >> ((DU * (hf + 1)) & 63)) & 1ull) != 0ull);
+      for (int k = 0; k < 32; ++k) wd[k] = (FULL || k < nvalid) ? gw[(32 * hf + k) * DPITCH + w] : 0u;
+      const unsigned m32 = (unsigned)(starts >> (32 * hf));
+      const bool ends = ge0 + 32 >= E || (hf == 0 ? ((starts >> 32) & 1ull) != 0ull
+                                                  : dnext != __builtin_amdgcn_readfirstlane(s[C::TM - 1]));
       float a0 = 0.f, a1 = 0.f;
       int k0 = 0;
-      bool sf = (mu & 1ull) != 0ull;   // the run at hand starts its row
-      auto flush = [&](bool ef) {
-        const int d = __builtin_amdgcn_readfirstlane(s[DU * hf + k0]);
-        float* o = (sf && ef) ? p.gP + (size_t)d * p.ldgP : p.dpart + ((size_t)(ge0 / DU) * 2 + (sf ? 1 : 0)) * H;
-        if constexpr (PAIRS) {
-          o[(w >> 5) * 64 + (w & 31)] = a0;
-          o[(w >> 5) * 64 + 32 + (w & 31)] = a1;
+      bool sf = (m32 & 1u) != 0u;   // the run at hand starts its row
+      bool first = true;            // ... and is the first one of this half
+      auto flush = [&](bool ef, bool last) {
+        const int d = __builtin_amdgcn_readfirstlane(s[32 * hf + k0]);
+        if (hf == 0 && last && cont) {
+          carry[w] = make_float2(a0, a1);
+        } else if (hf == 1 && first && cont) {
+          c0 = a0; c1 = a1; cd = d; cef = ef;
         } else {
-          o[w] = a0;
+          put(sf, ef, d, a0, a1);
         }
       };
 #pragma unroll
-      for (int k = 0; k < DU; ++k) {
-        if (__builtin_expect(k > 0 && ((mu >> k) & 1ull) && (FULL || k < nvalid), 0)) {   // about one edge in thirty
-          flush(true);
+      for (int k = 0; k < 32; ++k) {
+        if (__builtin_expect(k > 0 && ((m32 >> k) & 1u) && (FULL || k < nvalid), 0)) {   // about one edge in thirty
+          flush(true, false);
           a0 = a1 = 0.f;
           k0 = k;
           sf = true;
+          first = false;
         }
         if (FULL || k < nvalid) {
           if constexpr (PAIRS) {
@@ -1535,9 +1556,13 @@ __device__ __forceinline__ void edge_bwd_tile(const EdgeBwdArgs& p, unsigned cha
           }
         }
       }
-      flush(ends);
+      flush(ends, true);
     }
-    __syncthreads();   // the next tile's first phase writes the A tile again
+    __syncthreads();   // the next tile's first phase writes the A tile again; the carried parts are in LDS
+    if (hf == 1 && cont) {
+      const float2 c = carry[w];   // (written again two barriers into the next tile at the earliest)
+      put((starts & 0xffffffffull) != 0ull, cef, cd, c.x + c0, c.y + c1);
+    }
   }
 }
 
@@ -1631,7 +1656,8 @@ template <int H, bool BF16, bool ATTR, bool DSUM = false>
 static int32_t launch_edge_bwd_t(hipStream_t st, const EdgeBwdArgs& a) {
   using C = ECfg<H, BF16>;
   const int64_t ntiles = (a.E + C::TM - 1) / C::TM;
-  constexpr size_t lds = C::LDS_BYTES + 8 * C::TM * 4 + (ATTR ? 2 * (ATTR_TILE + ATTR_T_TILE) * 2 : 0);
+  static_assert(!(ATTR && DSUM), "the carried parts of the destination sums take the place of the attribute tiles");
+  constexpr size_t lds = C::LDS_BYTES + 8 * C::TM * 4 + (ATTR ? 2 * (ATTR_TILE + ATTR_T_TILE) * 2 : 0) + (DSUM ? 1024 : 0);
   static int per_cu = 0;
   if (!per_cu) {
     HGNN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_edge_bwd<H, BF16, ATTR, DSUM>),
