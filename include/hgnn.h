@@ -156,6 +156,11 @@ int32_t hgnn_embed_bwd_static(void* stream, int32_t N, int32_t H, const int32_t*
  * atom-level launches leave compute units idle, not used by the fused kernels, which fill the chip by themselves).
  * The environment variable HGNN_SIDE_STREAM = 0 / 1, read before the first call, sets the same. Returns the previous
  * setting (-1 / 0 / 1). The results do not depend on it bit for bit.
+ * _bwd needs dst sorted ascending and consistent with row_ptr (a destination-sorted CSR, as hgnn_radius_graph_fill
+ * writes it): with bf16 operands at H = 256 and with float32 operands at H = 128 the reverse edge kernel sums the
+ * gradients of an atom's incoming edges as runs of consecutive edges with equal dst. The environment variable
+ * HGNN_DSUM_IN_KERNEL = 0, read at every call, makes those sums a pass of its own over the edge tensor again (for
+ * comparing the two forms; the results then differ in the last places, both orders of addition are fixed).
  * The library keeps per-process state without locks: call it from one host thread at a time.
  * ------------------------------------------------------------------------------------------- */
 int32_t hgnn_set_side_stream(int32_t enable);
