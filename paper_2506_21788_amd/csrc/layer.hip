@@ -415,12 +415,13 @@ static int32_t mp_layer_bwd_impl(void* stream, int32_t N, int64_t E, int32_t H, 
   // every CU by itself, so the side stream is drained first instead of competing with it.
   HGNN_TRY(launch_edge_cvec(st, E, dst, rvec, g_v_out, alpha, w.cvec));
   HGNN_TRY(stream_after(st, sx, ss.ev[5]));
-  // With bf16 pairs, or fp32 operands at H = 128, the reverse edge kernel also sums g_z1 per destination (out of the tile it holds in LDS), unless
-  // the gradient with respect to d2 is asked for, which the separate pass over g_z1 forms on its way.
-  // HGNN_DSUM_IN_KERNEL=0 keeps the separate pass (for comparing the two).
+  // With bf16 pairs, or fp32 operands at H = 128, the reverse edge kernel also sums g_z1 per destination (out of the
+  // tile it holds in LDS). The gradient with respect to d2 (on request: the dot of every g_z1 row with the d2 row of
+  // W1) is then formed by the source-sorted pass, which reads every edge's row exactly once as well.
+  // HGNN_DSUM_IN_KERNEL=0 keeps the separate destination-sorted pass (for comparing the two).
   const char* dsum_env = getenv("HGNN_DSUM_IN_KERNEL");
   DsumFix dfix{nullptr, nullptr, nullptr, 0};
-  const bool dsum_in_kernel = edge_bwd_sums_dst(H, bf16) && k <= 1 && !g_d2 && N > 0 && !(dsum_env && dsum_env[0] == '0');
+  const bool dsum_in_kernel = edge_bwd_sums_dst(H, bf16) && k <= 1 && N > 0 && !(dsum_env && dsum_env[0] == '0');
   {
     EdgeBwdArgs e;
     e.E = E; e.dst = dst; e.col = col;
@@ -468,8 +469,11 @@ static int32_t mp_layer_bwd_impl(void* stream, int32_t N, int64_t E, int32_t H, 
                               W + o.W1 + 2 * HH, g_d2));
   }
   if (g_rvec) HGNN_TRY(launch_edge_grvec(st, E, dst, s.xe, g_v_out, alpha, g_rvec));
-  HGNN_TRY(launch_segsum_vm(st, H, bf16, N, colT_ptr, permT, w.gz1_vm, w.g_PQ + H, 2 * H, PT_SEGSUM_SRC, nullptr, nullptr,
-                            dsum_in_kernel ? &dfix : nullptr));  // g_Q
+  if (dsum_in_kernel)   // g_Q, the rows of g_P that cross tiles, and g_d2 where it is asked for
+    HGNN_TRY(launch_segsum_vm(st, H, bf16, N, colT_ptr, permT, w.gz1_vm, w.g_PQ + H, 2 * H, PT_SEGSUM_SRC,
+                              g_d2 ? W + o.W1 + 2 * HH : nullptr, g_d2, &dfix));
+  else
+    HGNN_TRY(launch_segsum_vm(st, H, bf16, N, colT_ptr, permT, w.gz1_vm, w.g_PQ + H, 2 * H, PT_SEGSUM_SRC));  // g_Q
   {  // g_h = (g_h' + g_h(a)) + g_P W1a^T + g_Q W1b^T
     GemmArgs g;
     g.A[0] = w.g_PQ; g.lda[0] = 2 * H; g.A[1] = w.g_PQ + H; g.lda[1] = 2 * H; g.nkc = 2;
